@@ -1,0 +1,212 @@
+"""Seeded synthetic inputs for the fused-array workloads.
+
+This module serves both the CPU oracle and the HIP path and therefore holds
+none of the method's arithmetic: it only draws random numbers, shapes them like
+the paper's workloads (point clouds of 2500 points / 16 classes standing in for
+ShapeNet-part, 64x64x3 images standing in for LSUN; section "Methodology",
+paragraph on PointNet and DCGAN) and lays them out as the operator fusion rules
+table prescribes (conv family ``[N, B*C, L]``, linear family ``[B, N, F]``).
+
+Everything is numpy; values destined for bf16 storage are snapped to
+bf16-representable float32 with ``torch``'s own cast (a library conversion, not
+ours) so that both sides start from identical bits.
+
+Model ``b`` draws from its own child stream, so its data does not depend on B.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# helpers
+# --------------------------------------------------------------------------
+def config_seed(config_index: int) -> int:
+    return 1000 * config_index + 7
+
+
+def model_streams(seed: int, B: int) -> List[np.random.Generator]:
+    """One independent generator per model, spawned in order of b."""
+    ss = np.random.SeedSequence(seed)
+    return [np.random.default_rng(s) for s in ss.spawn(B)]
+
+
+def snap(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Return float32 values exactly representable in the storage dtype."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype in ("f32", "f64"):     # "f64": oracle-only mode without storage rounding
+        return a
+    if dtype == "bf16":
+        import torch
+
+        return torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+    raise ValueError(dtype)
+
+
+def unit_ball_points(rng: np.random.Generator, n: int, L: int) -> np.ndarray:
+    """Points uniform in the unit ball, shape [n, 3, L]."""
+    d = rng.standard_normal((n, 3, L))
+    d /= np.linalg.norm(d, axis=1, keepdims=True)
+    r = rng.random((n, 1, L)) ** (1.0 / 3.0)
+    return d * r
+
+
+def uniform_fan_in(rng: np.random.Generator, shape: Sequence[int], fan_in: int,
+                   gain_sq: float) -> np.ndarray:
+    """U(-sqrt(gain_sq/fan_in), +sqrt(gain_sq/fan_in))."""
+    bound = math.sqrt(gain_sq / fan_in)
+    return rng.uniform(-bound, bound, size=tuple(shape))
+
+
+def log_uniform(rng: np.random.Generator, lo: float, hi: float) -> float:
+    return float(math.exp(rng.uniform(math.log(lo), math.log(hi))))
+
+
+# --------------------------------------------------------------------------
+# PointNet-classification-style fused array
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class PointNetClsSpec:
+    """Layer list of a PointNet-cls-style array (all models share it)."""
+    name: str
+    B: int
+    Nb: int                 # clouds per model per step
+    L: int                  # points per cloud
+    conv: Tuple[int, ...]   # channel chain of the per-point MLP, starts at 3
+    fc: Tuple[int, ...]     # channel chain after the pool, ends at n_classes
+    fc_bn: bool             # BatchNorm on the hidden FC layers
+    dropout_p: float        # dropout after the last hidden FC activation (0 = none)
+    dtype: str              # "f32" or "bf16" (storage; master weights fp32)
+    lr_range: Tuple[float, float] = (1e-4, 1e-2)
+    beta1_range: Optional[Tuple[float, float]] = None  # None -> 0.9 for all
+    n_classes: int = 16
+    config_index: int = 0
+
+
+def spec_c0() -> PointNetClsSpec:
+    return PointNetClsSpec(name="c0_pointnet_cls_B2_fp32", B=2, Nb=4, L=256,
+                           conv=(3, 64, 128, 1024), fc=(1024, 256, 16), fc_bn=False,
+                           dropout_p=0.0, dtype="f32", config_index=0)
+
+
+def spec_c1(B: int = 8, Nb: int = 32, L: int = 2500, dtype: str = "bf16") -> PointNetClsSpec:
+    return PointNetClsSpec(name=f"c1_pointnet_cls_B{B}_{dtype}", B=B, Nb=Nb, L=L,
+                           conv=(3, 64, 64, 64, 128, 1024), fc=(1024, 512, 256, 16),
+                           fc_bn=True, dropout_p=0.3, dtype=dtype,
+                           beta1_range=(0.8, 0.95), config_index=1)
+
+
+def pointnet_cls_param_shapes(spec: PointNetClsSpec) -> List[Tuple[str, Tuple[int, ...]]]:
+    """Per-model parameter list, in arena order.
+
+    conv weights are ``[Co, Ci]`` (kernel length 1), linear weights ``[Fx, Fy]``
+    as in the fusion rules table (baddbmm orientation).
+    """
+    out: List[Tuple[str, Tuple[int, ...]]] = []
+    for i in range(len(spec.conv) - 1):
+        ci, co = spec.conv[i], spec.conv[i + 1]
+        out += [(f"conv{i}.w", (co, ci)), (f"conv{i}.b", (co,)),
+                (f"conv{i}.bn.g", (co,)), (f"conv{i}.bn.b", (co,))]
+    nfc = len(spec.fc) - 1
+    for i in range(nfc):
+        fx, fy = spec.fc[i], spec.fc[i + 1]
+        out += [(f"fc{i}.w", (fx, fy)), (f"fc{i}.b", (fy,))]
+        if spec.fc_bn and i < nfc - 1:
+            out += [(f"fc{i}.bn.g", (fy,)), (f"fc{i}.bn.b", (fy,))]
+    return out
+
+
+def pointnet_cls_inputs(spec: PointNetClsSpec, seed: Optional[int] = None) -> Dict[str, object]:
+    """Draw everything one training step needs.
+
+    Returns a dict with
+      points   float32 [Nb, B*3, L]  (snapped to spec.dtype)
+      labels   int32   [B, Nb]
+      params   list over b of dict name -> float32 array (fp32 master values)
+      lr, beta1, beta2, eps, wd : float32 [B]
+      drop_mask uint8 [B, Nb, fc[-2]]  (1 = keep), or None
+    """
+    seed = config_seed(spec.config_index) if seed is None else seed
+    rngs = model_streams(seed, spec.B)
+    B, Nb, L = spec.B, spec.Nb, spec.L
+    points = np.empty((Nb, B * 3, L), dtype=np.float32)
+    labels = np.empty((B, Nb), dtype=np.int32)
+    params = []
+    lr = np.empty(B, np.float32)
+    beta1 = np.full(B, 0.9, np.float32)
+    beta2 = np.full(B, 0.999, np.float32)
+    eps = np.full(B, 1e-8, np.float32)
+    wd = np.zeros(B, np.float32)
+    mask = None
+    if spec.dropout_p > 0:
+        mask = np.empty((B, Nb, spec.fc[-2]), dtype=np.uint8)
+    for b, rng in enumerate(rngs):
+        points[:, 3 * b:3 * b + 3, :] = unit_ball_points(rng, Nb, L)
+        labels[b] = rng.integers(0, spec.n_classes, size=Nb)
+        p = {}
+        for name, shape in pointnet_cls_param_shapes(spec):
+            if name.endswith(".bn.g"):
+                p[name] = np.ones(shape, np.float32)
+            elif name.endswith(".bn.b"):
+                p[name] = np.zeros(shape, np.float32)
+            elif name.endswith(".w"):
+                fan_in = shape[1] if name.startswith("conv") else shape[0]
+                p[name] = uniform_fan_in(rng, shape, fan_in, 6.0).astype(np.float32)
+            else:  # bias of conv / linear: fan_in of the layer it belongs to
+                wshape = dict(pointnet_cls_param_shapes(spec))[name[:-2] + ".w"]
+                fan_in = wshape[1] if name.startswith("conv") else wshape[0]
+                p[name] = uniform_fan_in(rng, shape, fan_in, 1.0).astype(np.float32)
+        params.append(p)
+        lr[b] = log_uniform(rng, *spec.lr_range)
+        if spec.beta1_range is not None:
+            beta1[b] = rng.uniform(*spec.beta1_range)
+        if mask is not None:
+            mask[b] = (rng.random((Nb, spec.fc[-2])) >= spec.dropout_p).astype(np.uint8)
+    return dict(points=snap(points, spec.dtype), labels=labels, params=params,
+                lr=lr, beta1=beta1, beta2=beta2, eps=eps, wd=wd, drop_mask=mask)
+
+
+# --------------------------------------------------------------------------
+# operator-level cases (shapes of the other workloads)
+# --------------------------------------------------------------------------
+def normal(seed: int, shape: Sequence[int], dtype: str = "f32", scale: float = 1.0) -> np.ndarray:
+    rng = np.random.default_rng(seed)
+    return snap(rng.standard_normal(tuple(shape)) * scale, dtype)
+
+
+def uniform(seed: int, shape: Sequence[int], lo: float, hi: float, dtype: str = "f32") -> np.ndarray:
+    rng = np.random.default_rng(seed)
+    return snap(rng.uniform(lo, hi, size=tuple(shape)), dtype)
+
+
+def adam_hparams(seed: int, B: int, lr=(1e-4, 1e-2), beta1=(0.8, 0.95), beta2=(0.9, 0.999),
+                 wd=(0.0, 0.1)) -> Dict[str, np.ndarray]:
+    """Per-model optimiser hyper-parameter vectors (the fusible ones of the
+    hyper-parameter list table)."""
+    rng = np.random.default_rng(seed)
+    return dict(
+        lr=np.exp(rng.uniform(math.log(lr[0]), math.log(lr[1]), B)).astype(np.float32),
+        beta1=rng.uniform(*beta1, B).astype(np.float32),
+        beta2=rng.uniform(*beta2, B).astype(np.float32),
+        eps=np.full(B, 1e-8, np.float32),
+        wd=rng.uniform(*wd, B).astype(np.float32),
+    )
+
+
+# DCGAN layer table (BASELINE config 3): (Ci, Co, H_in, stride, pad); 4x4 kernels.
+DCGAN_D_LAYERS = ((3, 64, 64, 2, 1), (64, 128, 32, 2, 1), (128, 256, 16, 2, 1),
+                  (256, 512, 8, 2, 1), (512, 1, 4, 1, 0))
+# generator: transposed convolutions, listed as (Ci, Co, H_in, stride, pad)
+DCGAN_G_LAYERS = ((100, 512, 1, 1, 0), (512, 256, 4, 2, 1), (256, 128, 8, 2, 1),
+                  (128, 64, 16, 2, 1), (64, 3, 32, 2, 1))
+
+
+def dcgan_weights(seed: int, B: int, shape: Sequence[int], dtype: str = "bf16") -> np.ndarray:
+    """N(0, 0.02^2) weights, one set per model, concatenated on the leading dim."""
+    rngs = model_streams(seed, B)
+    w = np.concatenate([r.standard_normal(tuple(shape)) * 0.02 for r in rngs], axis=0)
+    return snap(w, dtype)
