@@ -1,0 +1,242 @@
+/*
+ * hfta.h -- C ABI of the horizontally fused training-array operators for one
+ * AMD Instinct MI355X (gfx950).
+ *
+ * B independent training jobs of one architecture (same operator shapes,
+ * different hyper-parameters) are run as ONE fused job: every operator below
+ * processes the tensors of all B models in one launch and is, per model,
+ * mathematically the ordinary single-model operator (paper section "Our
+ * Proposal: HFTA"; appendix "HFTA Operator Fusion Rules", the fusion rules
+ * table).  The kernels are hand-written HIP; nothing is delegated to a vendor
+ * library.
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ *  - Return value: HFTA_OK or a negative hfta_status.  No exceptions, aborts
+ *    or prints.  All argument validation happens before any launch, so every
+ *    HFTA_EINVAL / HFTA_EUNSUPPORTED / HFTA_EWORKSPACE path works on a host
+ *    without a GPU.
+ *  - Pointers are DEVICE pointers unless a comment says "host".  The caller
+ *    owns all memory; the library allocates nothing, frees nothing and keeps
+ *    no pointer after the call returns.  Scratch memory is a caller-supplied
+ *    `workspace` whose required size the matching *_workspace_bytes function
+ *    returns (0 = none needed; then NULL is accepted).
+ *  - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =
+ *    the default stream).  Outputs must not alias inputs unless stated.
+ *  - `dtype` is the storage type of activations, activation gradients and the
+ *    weights the GEMMs read: HFTA_F32 or HFTA_BF16.  Accumulation is always
+ *    fp32.  Parameter gradients (dW, dbias, dgamma, dbeta), BatchNorm /
+ *    LayerNorm statistics, optimiser state and master weights are always fp32.
+ *    A tensor stored in bf16 is rounded once, to nearest even, from the fp32
+ *    accumulator at the store.
+ *  - Strided activations: a tensor with logical index (b, n, c, l) -- model,
+ *    sample, channel, position -- is described by four element strides
+ *    s[4] = {stride_b, stride_n, stride_c, stride_l} (host array).  The
+ *    paper's convolution layout [N, B*C, L] is {C*L, B*C*L, L, 1}; its linear
+ *    layout [B, N, F] is {N*F, F, 1, -} with L = 1.
+ *  - Per-model hyper-parameters are device arrays of length B (fp32) that the
+ *    kernels read themselves (section "Our Proposal: HFTA", paragraph "HFTA
+ *    Optimizers and Learning Rate Schedulers").
+ *  - Sizes are limited to 2^31-1 elements per model slice where noted.
+ */
+#ifndef HFTA_H
+#define HFTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum hfta_status {
+  HFTA_OK = 0,
+  HFTA_EINVAL = -1,       /* null pointer, B <= 0, non-positive size, bad enum, overflow */
+  HFTA_EUNSUPPORTED = -2, /* valid but not implemented (dtype / stride / kernel-size combination) */
+  HFTA_EWORKSPACE = -3,   /* workspace missing or too small */
+  HFTA_ELAUNCH = -4       /* the HIP runtime reported an error at launch */
+} hfta_status;
+
+typedef enum hfta_dtype { HFTA_F32 = 0, HFTA_BF16 = 1 } hfta_dtype;
+
+typedef enum hfta_act {
+  HFTA_ACT_NONE = 0,
+  HFTA_ACT_RELU = 1,  /* max(x, 0); gradient 0 at x <= 0 */
+  HFTA_ACT_LEAKY = 2, /* x > 0 ? x : slope*x; gradient `slope` at x <= 0 */
+  HFTA_ACT_TANH = 3,
+  HFTA_ACT_GELU = 4   /* exact: x * Phi(x), Phi via erf */
+} hfta_act;
+
+const char* hfta_status_string(int status);
+int hfta_version(void);
+
+/* ------------------------------------------------------------------------
+ * Fused Linear (fusion rules table, row "Linear" -> baddbmm).
+ *   X:[B][M][Fx]  W:[B][Fx][Fy]  bias:[B][Fy] (or NULL)  Y:[B][M][Fy], all
+ *   contiguous, storage `dtype`.  Per model b: Y[b] = act(X[b] W[b] + bias[b]).
+ *   `act` is applied to the fp32 accumulator before the single store.
+ * ---------------------------------------------------------------------- */
+int hfta_linear_fwd(int B, int M, int Fx, int Fy, int dtype,
+                    const void* X, const void* W, const void* bias, void* Y,
+                    int act, float act_slope, void* stream);
+
+/* Backward of hfta_linear_fwd with act = NONE (apply hfta_act_bwd first otherwise).
+ *   dX[b] = dY[b] W[b]^T   (storage dtype; NULL = skip)
+ *   dW[b] = X[b]^T dY[b]   (fp32 [B][Fx][Fy]; NULL = skip)
+ *   dbias[b] = column sums of dY[b]  (fp32 [B][Fy]; NULL = skip)
+ * Workspace: hfta_linear_bwd_workspace_bytes (split-K partials of dW). */
+size_t hfta_linear_bwd_workspace_bytes(int B, int M, int Fx, int Fy, int dtype);
+int hfta_linear_bwd(int B, int M, int Fx, int Fy, int dtype,
+                    const void* X, const void* W, const void* dY,
+                    void* dX, float* dW, float* dbias,
+                    void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Fused Conv1d with kernel length 1 (row "Conv1d" -> grouped Conv1d, G = B).
+ *   X: logical [B][Nb][Ci][L] with strides xs; Y: [B][Nb][Co][L] with strides
+ *   ys; both need stride_l == 1.  W:[B][Co][Ci] contiguous (= the paper's
+ *   [B*Co, Ci, 1]), bias:[B][Co] or NULL, storage dtype.
+ *   Y[b,n,o,l] = act(bias[b,o] + sum_c W[b,o,c] X[b,n,c,l]).
+ * ---------------------------------------------------------------------- */
+int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                     const void* X, const int64_t xs[4], const void* W, const void* bias,
+                     void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
+
+/* Backward: dX[b,n,c,l] = sum_o W[b,o,c] dY[b,n,o,l]   (storage dtype, strides dxs; NULL = skip)
+ *           dW[b,o,c]   = sum_{n,l} dY[b,n,o,l] X[b,n,c,l]   (fp32; NULL = skip)
+ *           dbias[b,o]  = sum_{n,l} dY[b,n,o,l]              (fp32; NULL = skip)
+ * The reduction over n and l is split across workgroups; partial sums go to
+ * the workspace and are added in a fixed order (bit-reproducible). */
+size_t hfta_conv1x1_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
+int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                     const void* X, const int64_t xs[4], const void* W,
+                     const void* dY, const int64_t dys[4],
+                     void* dX, const int64_t dxs[4], float* dW, float* dbias,
+                     void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Fused Conv2d (row "Conv2d" -> grouped Conv2d with G = B; g = 1 per model).
+ *   X:[Nb][B*Ci][H][W]  Wt:[B*Co][Ci][kh][kw]  bias:[B*Co] or NULL
+ *   Y:[Nb][B*Co][Ho][Wo], Ho = (H + 2 pad - kh)/stride + 1, all contiguous.
+ *   Cross-correlation with zero padding, no dilation.
+ * The same two entry points serve the fused ConvTranspose2d (row "ConvT2d"):
+ *   ConvT fwd  (x:[Nb][B*Cx][H][W], w:[B*Cx][Cy][kh][kw]) = hfta_conv2d_grouped_bwd's dX
+ *              with dY := x, Wt := w, Ci := Cy, Co := Cx  (bias added by hfta_bias_act_nchw);
+ *   ConvT bwd-data = hfta_conv2d_grouped_fwd; ConvT dW = hfta_conv2d_grouped_bwd's dW with the
+ *              roles of X and dY exchanged the same way.
+ * ---------------------------------------------------------------------- */
+int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
+                            int stride, int pad, int dtype,
+                            const void* X, const void* Wt, const void* bias, void* Y,
+                            int act, float act_slope, void* stream);
+
+/* dX:[Nb][B*Ci][H][W] storage dtype (NULL = skip); dW: fp32 [B*Co][Ci][kh][kw] (NULL = skip);
+ * dbias: fp32 [B*Co] (NULL = skip). */
+size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W,
+                                               int kh, int kw, int stride, int pad, int dtype);
+int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
+                            int stride, int pad, int dtype,
+                            const void* X, const void* Wt, const void* dY,
+                            void* dX, float* dW, float* dbias,
+                            void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Fused BatchNorm, training mode (rows "BatchNorm1d", "BatchNorm2d").
+ *   X, Y: logical [B][Nb][C][L] with strides xs / ys; supported layouts:
+ *   stride_l == 1 (conv family; L = H*W for 2d) or L == 1 && stride_c == 1
+ *   (the table's [N, B, C] case).  gamma, beta, running_*, save_*: fp32 [B][C].
+ *   Per channel (b,c) over (n,l): mu = mean x; var = mean (x-mu)^2 (biased);
+ *   y = act(gamma (x-mu)/sqrt(var+eps) + beta);
+ *   running_mean <- (1-momentum) running_mean + momentum mu; running_var likewise
+ *   with the unbiased variance (skipped when running_mean == NULL).
+ *   save_mean / save_invstd receive mu and 1/sqrt(var+eps) for the backward.
+ *   Models never share statistics.
+ * ---------------------------------------------------------------------- */
+int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype,
+                const void* X, const int64_t xs[4], const float* gamma, const float* beta,
+                float eps, float momentum, float* running_mean, float* running_var,
+                float* save_mean, float* save_invstd,
+                void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
+
+/* Backward of hfta_bn_fwd including its fused activation (ReLU / LeakyReLU / NONE):
+ * the activation mask is recomputed from X and the saved statistics in fp32,
+ * exactly as the forward computed it.
+ *   dY: gradient w.r.t. the activated output; dX: gradient w.r.t. X (storage dtype);
+ *   dgamma, dbeta: fp32 [B][C]. */
+int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype,
+                const void* X, const int64_t xs[4], const void* dY, const int64_t dys[4],
+                const float* gamma, const float* beta,
+                const float* save_mean, const float* save_invstd,
+                void* dX, const int64_t dxs[4], float* dgamma, float* dbeta,
+                int act, float act_slope, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Max-pool over the point axis (PointNet's global feature; section
+ * "Methodology", PointNet workload).
+ *   X: logical [B][Nb][C][L], stride_l == 1.  V: logical [B][Nb][C] with strides
+ *   vs[3] = {stride_b, stride_n, stride_c} (so the result can land directly in
+ *   the linear layout [B][Nb][C]); idx: int32, same strides as V.
+ *   V = max_l X, idx = the LOWEST l attaining it.  NaN inputs: undefined.
+ * ---------------------------------------------------------------------- */
+int hfta_maxpool_points(int B, int Nb, int C, int L, int dtype,
+                        const void* X, const int64_t xs[4],
+                        void* V, int32_t* idx, const int64_t vs[3], void* stream);
+
+/* dX[b,n,c,l] = (l == idx[b,n,c]) ? dV[b,n,c] : 0; dX is fully written. */
+int hfta_maxpool_points_bwd(int B, int Nb, int C, int L, int dtype,
+                            const void* dV, const int32_t* idx, const int64_t vs[3],
+                            void* dX, const int64_t dxs[4], void* stream);
+
+/* ------------------------------------------------------------------------
+ * Fused Adam over the parameter arena of all B models (section "Our Proposal:
+ * HFTA", paragraph on optimizers: a vector of per-model learning rates applied
+ * to the concatenated gradients).
+ *   theta, m, v: fp32 [B][P], updated in place; grad: [B][P] in grad_dtype;
+ *   theta_lowp: bf16 [B][P] copy of the new theta (NULL = none);
+ *   lr, beta1, beta2, eps, weight_decay: fp32 [B] device arrays; step_t >= 1.
+ *   g' = g + wd theta (decoupled_wd = 0)  or  theta *= 1 - lr wd first (decoupled_wd = 1)
+ *   m = b1 m + (1-b1) g';  v = b2 v + (1-b2) g'^2
+ *   theta -= lr (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps)
+ * ---------------------------------------------------------------------- */
+int hfta_adam_step(int B, int64_t P, int grad_dtype,
+                   float* theta, const void* grad, float* m, float* v, void* theta_lowp,
+                   const float* lr, const float* beta1, const float* beta2, const float* eps,
+                   const float* weight_decay, int step_t, int decoupled_wd, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Support operators needed to close a training step (fusion rules table, rows
+ * "ReLU", "LeakyReLU", "Tanh", "Dropout", "LayerNorm"; appendix "Fused Loss").
+ * Elementwise operators work on `count` contiguous elements of any fused layout.
+ * ---------------------------------------------------------------------- */
+int hfta_act_fwd(int64_t count, int dtype, const void* X, void* Y, int act, float slope, void* stream);
+/* dX = dY * act'(.)  `from_output` != 0: Z holds the activation OUTPUT (valid for
+ * RELU, LEAKY with slope > 0, TANH); otherwise Z holds the pre-activation input. */
+int hfta_act_bwd(int64_t count, int dtype, const void* Z, const void* dY, void* dX,
+                 int act, float slope, int from_output, void* stream);
+/* Adds a per-channel bias to an [Nb][K][HW] tensor (K = B*C channels) and applies act, in place. */
+int hfta_bias_act_nchw(int64_t Nb, int64_t K, int64_t HW, int dtype, void* Y, const void* bias,
+                       int act, float slope, void* stream);
+/* Y = X * mask / (1-p); mask: uint8, 1 = keep; the same call is its own backward. */
+int hfta_dropout(int64_t count, int dtype, const void* X, const uint8_t* mask, float p, void* Y,
+                 void* stream);
+/* LayerNorm over the last dim E of X:[B][R][E] with per-model affine w,b: fp32 [B][E]. */
+int hfta_layernorm_fwd(int B, int R, int E, int dtype, const void* X, const float* w, const float* b,
+                       float eps, float* save_mean, float* save_invstd, void* Y, void* stream);
+size_t hfta_layernorm_bwd_workspace_bytes(int B, int R, int E);
+int hfta_layernorm_bwd(int B, int R, int E, int dtype, const void* X, const void* dY, const float* w,
+                       const float* save_mean, const float* save_invstd,
+                       void* dX, float* dw, float* db, void* workspace, size_t ws_bytes, void* stream);
+/* Per-model losses with mean reduction over the model's own R rows; loss: fp32 [B];
+ * dlogits in storage dtype.  No factor B appears because each model's loss is its
+ * own mean (appendix "Fused Loss", eq. 3). */
+int hfta_softmax_xent(int B, int R, int K, int dtype, const void* logits, const int32_t* labels,
+                      float* loss, void* dlogits, void* stream);
+int hfta_bce_logits(int B, int64_t R, int dtype, const void* logits, const void* targets,
+                    float* loss, void* dlogits, void* stream);
+int hfta_mse(int B, int64_t R, int dtype, const void* pred, const void* target,
+             float* loss, void* dpred, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HFTA_H */

@@ -1,0 +1,251 @@
+"""Thin ctypes binding over libhfta.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+``include/hfta.h``; tensors are ``torch`` CUDA tensors (used for device memory
+and streams only) or ``None``; stride arguments are Python sequences.  A
+non-zero status raises ``HftaError``.  There is no CPU fallback: if the library
+is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhfta.so")
+
+F32, BF16 = 0, 1
+ACT_NONE, ACT_RELU, ACT_LEAKY, ACT_TANH, ACT_GELU = 0, 1, 2, 3, 4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4
+
+
+class HftaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2102_02344_amd.build` "
+                          "(or __graft_entry__.build()) first")
+    return C.CDLL(LIB_PATH)
+
+
+_lib = _load()
+
+_i, _i64, _f, _p, _sz = C.c_int, C.c_int64, C.c_float, C.c_void_p, C.c_size_t
+_s4 = C.POINTER(C.c_int64)
+
+_SIGS = {
+    "hfta_status_string": (C.c_char_p, [_i]),
+    "hfta_version": (_i, []),
+    "hfta_linear_fwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _i, _f, _p]),
+    "hfta_linear_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
+    "hfta_linear_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
+    "hfta_conv1x1_fwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _s4, _i, _f, _p]),
+    "hfta_conv1x1_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
+    "hfta_conv1x1_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _p, _p, _p, _sz, _p]),
+    "hfta_conv2d_grouped_fwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _i, _f, _p]),
+    "hfta_conv2d_grouped_bwd_workspace_bytes": (_sz, [_i] * 11),
+    "hfta_conv2d_grouped_bwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _p, _p, _p, _sz, _p]),
+    "hfta_bn_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
+    "hfta_bn_bwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _i, _f, _p]),
+    "hfta_maxpool_points": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p]),
+    "hfta_maxpool_points_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _s4, _p, _s4, _p]),
+    "hfta_adam_step": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
+    "hfta_act_fwd": (_i, [_i64, _i, _p, _p, _i, _f, _p]),
+    "hfta_act_bwd": (_i, [_i64, _i, _p, _p, _p, _i, _f, _i, _p]),
+    "hfta_bias_act_nchw": (_i, [_i64, _i64, _i64, _i, _p, _p, _i, _f, _p]),
+    "hfta_dropout": (_i, [_i64, _i, _p, _p, _f, _p, _p]),
+    "hfta_layernorm_fwd": (_i, [_i, _i, _i, _i, _p, _p, _p, _f, _p, _p, _p, _p]),
+    "hfta_layernorm_bwd_workspace_bytes": (_sz, [_i, _i, _i]),
+    "hfta_layernorm_bwd": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
+    "hfta_softmax_xent": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p]),
+    "hfta_bce_logits": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p]),
+    "hfta_mse": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+EXPORTS = tuple(_SIGS)
+
+
+def status_string(status: int) -> str:
+    return _lib.hfta_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return _lib.hfta_version()
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a tensor (None -> NULL); raw ints pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _strides(s: Optional[Sequence[int]], n: int = 4):
+    if s is None:
+        return None
+    assert len(s) == n, (s, n)
+    return (C.c_int64 * n)(*[int(v) for v in s])
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != OK:
+        raise HftaError(rc, where)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+# ---------------------------------------------------------------- entry points
+def linear_fwd(B, M, Fx, Fy, dtype, X, W, bias, Y, act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_linear_fwd(B, M, Fx, Fy, dtype, _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), act, act_slope,
+                                _stream(stream)), "hfta_linear_fwd")
+
+
+def linear_bwd_workspace_bytes(B, M, Fx, Fy, dtype) -> int:
+    return _lib.hfta_linear_bwd_workspace_bytes(B, M, Fx, Fy, dtype)
+
+
+def linear_bwd(B, M, Fx, Fy, dtype, X, W, dY, dX, dW, dbias, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_linear_bwd(B, M, Fx, Fy, dtype, _ptr(X), _ptr(W), _ptr(dY), _ptr(dX), _ptr(dW), _ptr(dbias),
+                                wp, wb, _stream(stream)), "hfta_linear_bwd")
+
+
+def conv1x1_fwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Y, ys, act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_conv1x1_fwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(bias), _ptr(Y),
+                                 _strides(ys), act, act_slope, _stream(stream)), "hfta_conv1x1_fwd")
+
+
+def conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype) -> int:
+    return _lib.hfta_conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype)
+
+
+def conv1x1_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, dY, dys, dX, dxs, dW, dbias, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_conv1x1_bwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(dY), _strides(dys),
+                                 _ptr(dX), _strides(dxs), _ptr(dW), _ptr(dbias), wp, wb, _stream(stream)),
+           "hfta_conv1x1_bwd")
+
+
+def conv2d_grouped_fwd(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype, X, Wt, bias, Y, act=ACT_NONE,
+                       act_slope=0.0, stream=None):
+    _check(_lib.hfta_conv2d_grouped_fwd(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype, _ptr(X), _ptr(Wt),
+                                        _ptr(bias), _ptr(Y), act, act_slope, _stream(stream)),
+           "hfta_conv2d_grouped_fwd")
+
+
+def conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype) -> int:
+    return _lib.hfta_conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype)
+
+
+def conv2d_grouped_bwd(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype, X, Wt, dY, dX, dW, dbias,
+                       workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_conv2d_grouped_bwd(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype, _ptr(X), _ptr(Wt),
+                                        _ptr(dY), _ptr(dX), _ptr(dW), _ptr(dbias), wp, wb, _stream(stream)),
+           "hfta_conv2d_grouped_bwd")
+
+
+def bn_fwd(B, Nb, C_, L, dtype, X, xs, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
+           save_invstd, Y, ys, act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_bn_fwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(gamma), _ptr(beta), eps, momentum,
+                            _ptr(running_mean), _ptr(running_var), _ptr(save_mean), _ptr(save_invstd), _ptr(Y),
+                            _strides(ys), act, act_slope, _stream(stream)), "hfta_bn_fwd")
+
+
+def bn_bwd(B, Nb, C_, L, dtype, X, xs, dY, dys, gamma, beta, save_mean, save_invstd, dX, dxs, dgamma, dbeta,
+           act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_bn_bwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(dY), _strides(dys), _ptr(gamma),
+                            _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dX), _strides(dxs), _ptr(dgamma),
+                            _ptr(dbeta), act, act_slope, _stream(stream)), "hfta_bn_bwd")
+
+
+def maxpool_points(B, Nb, C_, L, dtype, X, xs, V, idx, vs, stream=None):
+    _check(_lib.hfta_maxpool_points(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(V), _ptr(idx),
+                                    _strides(vs, 3), _stream(stream)), "hfta_maxpool_points")
+
+
+def maxpool_points_bwd(B, Nb, C_, L, dtype, dV, idx, vs, dX, dxs, stream=None):
+    _check(_lib.hfta_maxpool_points_bwd(B, Nb, C_, L, dtype, _ptr(dV), _ptr(idx), _strides(vs, 3), _ptr(dX),
+                                        _strides(dxs), _stream(stream)), "hfta_maxpool_points_bwd")
+
+
+def adam_step(B, P, grad_dtype, theta, grad, m, v, theta_lowp, lr, beta1, beta2, eps, weight_decay, step_t,
+              decoupled_wd=0, stream=None):
+    _check(_lib.hfta_adam_step(B, P, grad_dtype, _ptr(theta), _ptr(grad), _ptr(m), _ptr(v), _ptr(theta_lowp),
+                               _ptr(lr), _ptr(beta1), _ptr(beta2), _ptr(eps), _ptr(weight_decay), step_t,
+                               decoupled_wd, _stream(stream)), "hfta_adam_step")
+
+
+def act_fwd(count, dtype, X, Y, act, slope=0.0, stream=None):
+    _check(_lib.hfta_act_fwd(count, dtype, _ptr(X), _ptr(Y), act, slope, _stream(stream)), "hfta_act_fwd")
+
+
+def act_bwd(count, dtype, Z, dY, dX, act, slope=0.0, from_output=0, stream=None):
+    _check(_lib.hfta_act_bwd(count, dtype, _ptr(Z), _ptr(dY), _ptr(dX), act, slope, from_output, _stream(stream)),
+           "hfta_act_bwd")
+
+
+def bias_act_nchw(Nb, K, HW, dtype, Y, bias, act=ACT_NONE, slope=0.0, stream=None):
+    _check(_lib.hfta_bias_act_nchw(Nb, K, HW, dtype, _ptr(Y), _ptr(bias), act, slope, _stream(stream)),
+           "hfta_bias_act_nchw")
+
+
+def dropout(count, dtype, X, mask, p, Y, stream=None):
+    _check(_lib.hfta_dropout(count, dtype, _ptr(X), _ptr(mask), p, _ptr(Y), _stream(stream)), "hfta_dropout")
+
+
+def layernorm_fwd(B, R, E, dtype, X, w, b, eps, save_mean, save_invstd, Y, stream=None):
+    _check(_lib.hfta_layernorm_fwd(B, R, E, dtype, _ptr(X), _ptr(w), _ptr(b), eps, _ptr(save_mean),
+                                   _ptr(save_invstd), _ptr(Y), _stream(stream)), "hfta_layernorm_fwd")
+
+
+def layernorm_bwd_workspace_bytes(B, R, E) -> int:
+    return _lib.hfta_layernorm_bwd_workspace_bytes(B, R, E)
+
+
+def layernorm_bwd(B, R, E, dtype, X, dY, w, save_mean, save_invstd, dX, dw, db, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_layernorm_bwd(B, R, E, dtype, _ptr(X), _ptr(dY), _ptr(w), _ptr(save_mean), _ptr(save_invstd),
+                                   _ptr(dX), _ptr(dw), _ptr(db), wp, wb, _stream(stream)), "hfta_layernorm_bwd")
+
+
+def softmax_xent(B, R, K, dtype, logits, labels, loss, dlogits, stream=None):
+    _check(_lib.hfta_softmax_xent(B, R, K, dtype, _ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits),
+                                  _stream(stream)), "hfta_softmax_xent")
+
+
+def bce_logits(B, R, dtype, logits, targets, loss, dlogits, stream=None):
+    _check(_lib.hfta_bce_logits(B, R, dtype, _ptr(logits), _ptr(targets), _ptr(loss), _ptr(dlogits),
+                                _stream(stream)), "hfta_bce_logits")
+
+
+def mse(B, R, dtype, pred, target, loss, dpred, stream=None):
+    _check(_lib.hfta_mse(B, R, dtype, _ptr(pred), _ptr(target), _ptr(loss), _ptr(dpred), _stream(stream)), "hfta_mse")
+
+
+def raw():
+    """The ctypes library handle (for status-code tests that must not raise)."""
+    return _lib

@@ -1,0 +1,303 @@
+// Fused BatchNorm (training mode) over the channels of all B models.
+//
+// Conv-family layout (stride_l == 1): one workgroup per channel (b, c).  It
+// streams the channel's Nb rows of L contiguous elements twice -- once for the
+// statistics, once to normalise -- and the second pass of a channel follows its
+// first immediately, so the re-read is served by L2 / Infinity Cache rather
+// than HBM for all but the largest channels.  Statistics use sums shifted by
+// the channel's first element, which keeps fp32 accurate when |mean| >> std.
+// Reductions: per-lane partials -> wave64 shuffle reduction -> 4-entry LDS.
+//
+// Linear layout (L == 1, stride_c == 1, the table's [N, B, C] case): one thread
+// per channel, coalesced across channels, two passes over the Nb samples.
+#include "common.h"
+
+using namespace hfta;
+
+namespace {
+
+template <typename T, int VEC> struct Vec;
+template <> struct Vec<float, 4> { typedef float4 type; };
+template <> struct Vec<float, 1> { typedef float type; };
+template <> struct Vec<bf16_raw, 4> { typedef uint2 type; };
+template <> struct Vec<bf16_raw, 1> { typedef bf16_raw type; };
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_vec(const T* p, float (&v)[VEC]) {
+  typename Vec<T, VEC>::type raw = *reinterpret_cast<const typename Vec<T, VEC>::type*>(p);
+  const T* e = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) v[i] = Elem<T>::to_f32(e[i]);
+}
+template <typename T, int VEC>
+__device__ __forceinline__ void store_vec(T* p, const float (&v)[VEC]) {
+  typename Vec<T, VEC>::type raw;
+  T* e = reinterpret_cast<T*>(&raw);
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) e[i] = Elem<T>::from_f32(v[i]);
+  *reinterpret_cast<typename Vec<T, VEC>::type*>(p) = raw;
+}
+
+// block-wide sum of two values; result valid in every thread
+__device__ __forceinline__ void block_sum2(float& a, float& b, float (*sh)[2]) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { sh[w][0] = a; sh[w][1] = b; }
+  __syncthreads();
+  a = (sh[0][0] + sh[1][0]) + (sh[2][0] + sh[3][0]);
+  b = (sh[0][1] + sh[1][1]) + (sh[2][1] + sh[3][1]);
+}
+
+__device__ __forceinline__ float act_grad(float pre, int act, float slope) {
+  if (act == HFTA_ACT_RELU) return pre > 0.f ? 1.f : 0.f;
+  if (act == HFTA_ACT_LEAKY) return pre > 0.f ? 1.f : slope;
+  return 1.f;
+}
+
+struct BnFwdArgs {
+  const void* X; void* Y;
+  const float* gamma; const float* beta;
+  float* running_mean; float* running_var; float* save_mean; float* save_invstd;
+  int64_t xsb, xsn, xsc, ysb, ysn, ysc;
+  int Nb, C, L, act;
+  float eps, momentum, slope;
+};
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void bn_fwd_conv_kernel(BnFwdArgs p) {
+  __shared__ float sh[4][2];
+  const int c = blockIdx.x, b = blockIdx.y;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
+  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
+  const int chunks = p.L / VEC;
+  const int64_t total = (int64_t)p.Nb * chunks;
+  const float shift = Elem<T>::load(x);
+  float s1 = 0.f, s2 = 0.f;
+  for (int64_t i = threadIdx.x; i < total; i += 256) {
+    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+    float v[VEC];
+    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { const float d = v[e] - shift; s1 += d; s2 = fmaf(d, d, s2); }
+  }
+  block_sum2(s1, s2, sh);
+  const float m = (float)p.Nb * (float)p.L;
+  const float dm = s1 / m;
+  const float mean = shift + dm;
+  float var = s2 / m - dm * dm;
+  var = var < 0.f ? 0.f : var;
+  const float invstd = 1.0f / sqrtf(var + p.eps);
+  const int k = b * p.C + c;
+  const float g = p.gamma[k], bt = p.beta[k];
+  if (threadIdx.x == 0) {
+    p.save_mean[k] = mean;
+    p.save_invstd[k] = invstd;
+    if (p.running_mean) {
+      const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
+      p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
+      p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
+    }
+  }
+  for (int64_t i = threadIdx.x; i < total; i += 256) {
+    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+    float v[VEC];
+    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) v[e] = apply_act(fmaf(g, (v[e] - mean) * invstd, bt), p.act, p.slope);
+    store_vec<T, VEC>(y + n * p.ysn + ch * VEC, v);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_fwd_linear_kernel(BnFwdArgs p) {
+  const int c = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
+  if (c >= p.C) return;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c;
+  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c;
+  float s = 0.f;
+  for (int n = 0; n < p.Nb; ++n) s += Elem<T>::load(x + n * p.xsn);
+  const float m = (float)p.Nb;
+  const float mean = s / m;
+  float q = 0.f;
+  for (int n = 0; n < p.Nb; ++n) { const float d = Elem<T>::load(x + n * p.xsn) - mean; q = fmaf(d, d, q); }
+  const float var = q / m;
+  const float invstd = 1.0f / sqrtf(var + p.eps);
+  const int k = b * p.C + c;
+  const float g = p.gamma[k], bt = p.beta[k];
+  p.save_mean[k] = mean;
+  p.save_invstd[k] = invstd;
+  if (p.running_mean) {
+    const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
+    p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
+    p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
+  }
+  for (int n = 0; n < p.Nb; ++n) {
+    const float v = Elem<T>::load(x + n * p.xsn);
+    Elem<T>::store(y + n * p.ysn, apply_act(fmaf(g, (v - mean) * invstd, bt), p.act, p.slope));
+  }
+}
+
+struct BnBwdArgs {
+  const void* X; const void* dY; void* dX;
+  const float* gamma; const float* beta; const float* save_mean; const float* save_invstd;
+  float* dgamma; float* dbeta;
+  int64_t xsb, xsn, xsc, dysb, dysn, dysc, dxsb, dxsn, dxsc;
+  int Nb, C, L, act;
+  float slope;
+};
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void bn_bwd_conv_kernel(BnBwdArgs p) {
+  __shared__ float sh[4][2];
+  const int c = blockIdx.x, b = blockIdx.y, k = b * p.C + c;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
+  const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + c * p.dysc;
+  T* dx = reinterpret_cast<T*>(p.dX) + b * p.dxsb + c * p.dxsc;
+  const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
+  const int chunks = p.L / VEC;
+  const int64_t total = (int64_t)p.Nb * chunks;
+  float s1 = 0.f, s2 = 0.f;
+  for (int64_t i = threadIdx.x; i < total; i += 256) {
+    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+    float v[VEC], d[VEC];
+    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
+    load_vec<T, VEC>(dy + n * p.dysn + ch * VEC, d);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float xh = (v[e] - mean) * invstd;
+      const float gr = d[e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+      s1 += gr;
+      s2 = fmaf(gr, xh, s2);
+    }
+  }
+  block_sum2(s1, s2, sh);
+  if (threadIdx.x == 0) { p.dbeta[k] = s1; p.dgamma[k] = s2; }
+  const float m = (float)p.Nb * (float)p.L;
+  const float mb = s1 / m, mg = s2 / m, sc = g * invstd;
+  for (int64_t i = threadIdx.x; i < total; i += 256) {
+    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+    float v[VEC], d[VEC];
+    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
+    load_vec<T, VEC>(dy + n * p.dysn + ch * VEC, d);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float xh = (v[e] - mean) * invstd;
+      const float gr = d[e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+      v[e] = sc * (gr - mb - xh * mg);
+    }
+    store_vec<T, VEC>(dx + n * p.dxsn + ch * VEC, v);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_linear_kernel(BnBwdArgs p) {
+  const int c = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
+  if (c >= p.C) return;
+  const int k = b * p.C + c;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c;
+  const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + c;
+  T* dx = reinterpret_cast<T*>(p.dX) + b * p.dxsb + c;
+  const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
+  float s1 = 0.f, s2 = 0.f;
+  for (int n = 0; n < p.Nb; ++n) {
+    const float xh = (Elem<T>::load(x + n * p.xsn) - mean) * invstd;
+    const float gr = Elem<T>::load(dy + n * p.dysn) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+    s1 += gr;
+    s2 = fmaf(gr, xh, s2);
+  }
+  p.dbeta[k] = s1;
+  p.dgamma[k] = s2;
+  const float m = (float)p.Nb, mb = s1 / m, mg = s2 / m, sc = g * invstd;
+  for (int n = 0; n < p.Nb; ++n) {
+    const float xh = (Elem<T>::load(x + n * p.xsn) - mean) * invstd;
+    const float gr = Elem<T>::load(dy + n * p.dysn) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+    Elem<T>::store(dx + n * p.dxsn, sc * (gr - mb - xh * mg));
+  }
+}
+
+bool vec_ok(const void* p, const int64_t* s, int L, int dtype) {
+  const int es = (int)dtype_size(dtype);
+  const size_t bytes = 4 * es;
+  return L % 4 == 0 && reinterpret_cast<uintptr_t>(p) % bytes == 0 && s[0] % 4 == 0 && s[1] % 4 == 0 && s[2] % 4 == 0;
+}
+
+int layout_kind(const int64_t* s, int L) {
+  if (s[3] == 1) return 1;                 // conv family
+  if (L == 1 && s[2] == 1) return 2;       // linear family
+  return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
+                const float* beta, float eps, float momentum, float* running_mean, float* running_var,
+                float* save_mean, float* save_invstd, void* Y, const int64_t ys[4], int act, float act_slope,
+                void* stream) {
+  if (B <= 0 || Nb <= 0 || C <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !gamma || !beta || !save_mean ||
+      !save_invstd || !Y || !ys || !(eps >= 0.f))
+    return HFTA_EINVAL;
+  if ((running_mean == nullptr) != (running_var == nullptr)) return HFTA_EINVAL;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (B > 65535) return HFTA_EUNSUPPORTED;
+  const bool lin = (L == 1 && xs[2] == 1 && ys[2] == 1);
+  const int kx = lin ? 2 : layout_kind(xs, L), ky = lin ? 2 : layout_kind(ys, L);
+  if (kx == 0 || kx != ky) return HFTA_EUNSUPPORTED;
+  BnFwdArgs a{X, Y, gamma, beta, running_mean, running_var, save_mean, save_invstd,
+              xs[0], xs[1], xs[2], ys[0], ys[1], ys[2], Nb, C, L, act, eps, momentum, act_slope};
+  hipStream_t st = as_stream(stream);
+  if (kx == 2) {
+    dim3 grid((unsigned)((C + 255) / 256), (unsigned)B);
+    if (dtype == HFTA_BF16) hipLaunchKernelGGL(bn_fwd_linear_kernel<bf16_raw>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(bn_fwd_linear_kernel<float>, grid, dim3(256), 0, st, a);
+    return launch_status();
+  }
+  dim3 grid((unsigned)C, (unsigned)B);
+  const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
+  if (dtype == HFTA_BF16) {
+    if (v4) hipLaunchKernelGGL((bn_fwd_conv_kernel<bf16_raw, 4>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((bn_fwd_conv_kernel<bf16_raw, 1>), grid, dim3(256), 0, st, a);
+  } else {
+    if (v4) hipLaunchKernelGGL((bn_fwd_conv_kernel<float, 4>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((bn_fwd_conv_kernel<float, 1>), grid, dim3(256), 0, st, a);
+  }
+  return launch_status();
+}
+
+int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const void* dY,
+                const int64_t dys[4], const float* gamma, const float* beta, const float* save_mean,
+                const float* save_invstd, void* dX, const int64_t dxs[4], float* dgamma, float* dbeta, int act,
+                float act_slope, void* stream) {
+  if (B <= 0 || Nb <= 0 || C <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !dY || !dys || !gamma || !beta ||
+      !save_mean || !save_invstd || !dX || !dxs || !dgamma || !dbeta)
+    return HFTA_EINVAL;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (B > 65535) return HFTA_EUNSUPPORTED;
+  const bool lin = (L == 1 && xs[2] == 1 && dys[2] == 1 && dxs[2] == 1);
+  const int kx = lin ? 2 : layout_kind(xs, L);
+  if (kx == 0 || (!lin && (layout_kind(dys, L) != kx || layout_kind(dxs, L) != kx))) return HFTA_EUNSUPPORTED;
+  BnBwdArgs a{X, dY, dX, gamma, beta, save_mean, save_invstd, dgamma, dbeta,
+              xs[0], xs[1], xs[2], dys[0], dys[1], dys[2], dxs[0], dxs[1], dxs[2], Nb, C, L, act, act_slope};
+  hipStream_t st = as_stream(stream);
+  if (kx == 2) {
+    dim3 grid((unsigned)((C + 255) / 256), (unsigned)B);
+    if (dtype == HFTA_BF16) hipLaunchKernelGGL(bn_bwd_linear_kernel<bf16_raw>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(bn_bwd_linear_kernel<float>, grid, dim3(256), 0, st, a);
+    return launch_status();
+  }
+  dim3 grid((unsigned)C, (unsigned)B);
+  const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(dY, dys, L, dtype) && vec_ok(dX, dxs, L, dtype);
+  if (dtype == HFTA_BF16) {
+    if (v4) hipLaunchKernelGGL((bn_bwd_conv_kernel<bf16_raw, 4>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((bn_bwd_conv_kernel<bf16_raw, 1>), grid, dim3(256), 0, st, a);
+  } else {
+    if (v4) hipLaunchKernelGGL((bn_bwd_conv_kernel<float, 4>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((bn_bwd_conv_kernel<float, 1>), grid, dim3(256), 0, st, a);
+  }
+  return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,368 @@
+// Support operators that close a training step: activations, dropout from an
+// explicit mask, per-model LayerNorm, per-model losses.  All are HBM-bound
+// streaming kernels; per-model reductions never mix models.
+#include "common.h"
+
+using namespace hfta;
+
+namespace {
+
+__device__ __forceinline__ float act_deriv_from_input(float x, int act, float slope) {
+  switch (act) {
+    case HFTA_ACT_RELU: return x > 0.f ? 1.f : 0.f;
+    case HFTA_ACT_LEAKY: return x > 0.f ? 1.f : slope;
+    case HFTA_ACT_TANH: { const float t = tanhf(x); return 1.f - t * t; }
+    case HFTA_ACT_GELU: {
+      const float cdf = 0.5f * (1.f + erff(x * 0.70710678118654752f));
+      const float pdf = 0.39894228040143268f * expf(-0.5f * x * x);
+      return cdf + x * pdf;
+    }
+    default: return 1.f;
+  }
+}
+__device__ __forceinline__ float act_deriv_from_output(float y, int act, float slope) {
+  switch (act) {
+    case HFTA_ACT_RELU: return y > 0.f ? 1.f : 0.f;
+    case HFTA_ACT_LEAKY: return y > 0.f ? 1.f : slope;
+    case HFTA_ACT_TANH: return 1.f - y * y;
+    default: return 1.f;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void act_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t n, int act, float slope) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    Elem<T>::store(y + i, apply_act(Elem<T>::load(x + i), act, slope));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void act_bwd_kernel(const T* __restrict__ z, const T* __restrict__ dy, T* __restrict__ dx,
+                                                     int64_t n, int act, float slope, int from_output) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const float zz = Elem<T>::load(z + i);
+    const float d = from_output ? act_deriv_from_output(zz, act, slope) : act_deriv_from_input(zz, act, slope);
+    Elem<T>::store(dx + i, Elem<T>::load(dy + i) * d);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bias_act_nchw_kernel(T* __restrict__ y, const T* __restrict__ bias, int64_t K, int64_t HW,
+                                                           int64_t total, int act, float slope) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t k = (i / HW) % K;
+    const float b = bias ? Elem<T>::load(bias + k) : 0.f;
+    Elem<T>::store(y + i, apply_act(Elem<T>::load(y + i) + b, act, slope));
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void dropout_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask, T* __restrict__ y,
+                                                     int64_t n, float scale) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    Elem<T>::store(y + i, mask[i] ? Elem<T>::load(x + i) * scale : 0.f);
+}
+
+// ---- LayerNorm: one wavefront per row of E elements -----------------------
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict__ X, const float* __restrict__ w,
+                                                           const float* __restrict__ bsh, float eps, float* __restrict__ save_mean,
+                                                           float* __restrict__ save_invstd, T* __restrict__ Y, int R, int E,
+                                                           int64_t rows) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int b = (int)(row / R);
+  const T* x = X + row * E;
+  float s = 0.f;
+  for (int e = lane; e < E; e += 64) s += Elem<T>::load(x + e);
+  const float mean = wave_sum(s) / (float)E;
+  float q = 0.f;
+  for (int e = lane; e < E; e += 64) { const float d = Elem<T>::load(x + e) - mean; q = fmaf(d, d, q); }
+  const float invstd = 1.0f / sqrtf(wave_sum(q) / (float)E + eps);
+  if (lane == 0) { save_mean[row] = mean; save_invstd[row] = invstd; }
+  const float* wb = w + (int64_t)b * E;
+  const float* bb = bsh + (int64_t)b * E;
+  T* y = Y + row * E;
+  for (int e = lane; e < E; e += 64)
+    Elem<T>::store(y + e, fmaf((Elem<T>::load(x + e) - mean) * invstd, wb[e], bb[e]));
+}
+
+// dx per row; per-block partial dw/db over its rows go to the workspace [nblk][2][E] per model
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict__ X, const T* __restrict__ dY, const float* __restrict__ w,
+                                                           const float* __restrict__ save_mean, const float* __restrict__ save_invstd,
+                                                           T* __restrict__ dX, float* __restrict__ part, int R, int E, int rows_per_block) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int b = blockIdx.y;
+  const int r_begin = blockIdx.x * rows_per_block;
+  const int r_end = min(R, r_begin + rows_per_block);
+  const float* wb = w + (int64_t)b * E;
+  for (int r = r_begin + wv; r < r_end; r += 4) {
+    const int64_t row = (int64_t)b * R + r;
+    const T* x = X + row * E;
+    const T* dy = dY + row * E;
+    const float mean = save_mean[row], invstd = save_invstd[row];
+    float s1 = 0.f, s2 = 0.f;
+    for (int e = lane; e < E; e += 64) {
+      const float g = Elem<T>::load(dy + e) * wb[e];
+      const float xh = (Elem<T>::load(x + e) - mean) * invstd;
+      s1 += g; s2 = fmaf(g, xh, s2);
+    }
+    s1 = wave_sum(s1) / (float)E;
+    s2 = wave_sum(s2) / (float)E;
+    T* dx = dX + row * E;
+    for (int e = lane; e < E; e += 64) {
+      const float g = Elem<T>::load(dy + e) * wb[e];
+      const float xh = (Elem<T>::load(x + e) - mean) * invstd;
+      Elem<T>::store(dx + e, invstd * (g - s1 - xh * s2));
+    }
+  }
+  // column partials: thread t owns columns t, t+256, ... and walks this block's rows in order
+  float* pw = part + (((int64_t)b * gridDim.x + blockIdx.x) * 2) * E;
+  for (int e = threadIdx.x; e < E; e += 256) {
+    float aw = 0.f, ab = 0.f;
+    for (int r = r_begin; r < r_end; ++r) {
+      const int64_t row = (int64_t)b * R + r;
+      const float d = Elem<T>::load(dY + row * E + e);
+      const float xh = (Elem<T>::load(X + row * E + e) - save_mean[row]) * save_invstd[row];
+      aw = fmaf(d, xh, aw); ab += d;
+    }
+    pw[e] = aw; pw[E + e] = ab;
+  }
+}
+
+__global__ __launch_bounds__(256) void layernorm_bwd_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                                  float* __restrict__ db, int E, int nblk) {
+  const int b = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= E) return;
+  float aw = 0.f, ab = 0.f;
+  for (int k = 0; k < nblk; ++k) {
+    const float* pw = part + (((int64_t)b * nblk + k) * 2) * E;
+    aw += pw[e]; ab += pw[E + e];
+  }
+  dw[(int64_t)b * E + e] = aw;
+  db[(int64_t)b * E + e] = ab;
+}
+
+// ---- losses: one workgroup per model, fixed reduction order ----------------
+__device__ __forceinline__ float block_sum_1024(float v, float* sh) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float s = 0.f;
+  const int nw = blockDim.x >> 6;
+  for (int i = 0; i < nw; ++i) s += sh[i];
+  return s;
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024) void softmax_xent_kernel(const T* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                           float* __restrict__ loss, T* __restrict__ dlogits, int R, int K) {
+  __shared__ float sh[16];
+  const int b = blockIdx.x;
+  float acc = 0.f;
+  const float invR = 1.f / (float)R;
+  for (int r = threadIdx.x; r < R; r += blockDim.x) {
+    const T* z = logits + ((int64_t)b * R + r) * K;
+    T* dz = dlogits + ((int64_t)b * R + r) * K;
+    const int lab = labels[(int64_t)b * R + r];
+    float mx = -INFINITY;
+    for (int k = 0; k < K; ++k) mx = fmaxf(mx, Elem<T>::load(z + k));
+    float se = 0.f;
+    for (int k = 0; k < K; ++k) se += expf(Elem<T>::load(z + k) - mx);
+    const float lse = mx + logf(se);
+    acc += lse - Elem<T>::load(z + lab);
+    for (int k = 0; k < K; ++k) {
+      const float pk = expf(Elem<T>::load(z + k) - lse);
+      Elem<T>::store(dz + k, (pk - (k == lab ? 1.f : 0.f)) * invR);
+    }
+  }
+  const float s = block_sum_1024(acc, sh);
+  if (threadIdx.x == 0) loss[b] = s * invR;
+}
+
+template <typename T, int KIND>  // KIND 0: BCE on sigmoid(logits); 1: MSE
+__global__ __launch_bounds__(1024) void pointwise_loss_kernel(const T* __restrict__ pred, const T* __restrict__ target,
+                                                             float* __restrict__ loss, T* __restrict__ dpred, int64_t R) {
+  __shared__ float sh[16];
+  const int b = blockIdx.x;
+  float acc = 0.f;
+  const float invR = 1.f / (float)R;
+  for (int64_t i = threadIdx.x; i < R; i += blockDim.x) {
+    const float z = Elem<T>::load(pred + (int64_t)b * R + i);
+    const float t = Elem<T>::load(target + (int64_t)b * R + i);
+    float g;
+    if (KIND == 0) {
+      acc += fmaxf(z, 0.f) - z * t + log1pf(expf(-fabsf(z)));
+      g = 1.f / (1.f + expf(-z)) - t;
+    } else {
+      const float d = z - t;
+      acc = fmaf(d, d, acc);
+      g = 2.f * d;
+    }
+    Elem<T>::store(dpred + (int64_t)b * R + i, g * invR);
+  }
+  const float s = block_sum_1024(acc, sh);
+  if (threadIdx.x == 0) loss[b] = s * invR;
+}
+
+unsigned stream_blocks(int64_t n) {
+  int64_t b = (n + 255) / 256;
+  const int64_t cap = 256 * 32;
+  return (unsigned)(b > cap ? cap : (b < 1 ? 1 : b));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hfta_status_string(int status) {
+  switch (status) {
+    case HFTA_OK: return "ok";
+    case HFTA_EINVAL: return "invalid argument";
+    case HFTA_EUNSUPPORTED: return "unsupported dtype / stride / size combination";
+    case HFTA_EWORKSPACE: return "workspace missing or too small";
+    case HFTA_ELAUNCH: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int hfta_version(void) { return 100; }
+
+int hfta_act_fwd(int64_t count, int dtype, const void* X, void* Y, int act, float slope, void* stream) {
+  if (count <= 0 || !valid_dtype(dtype) || !X || !Y || !valid_act(act)) return HFTA_EINVAL;
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(act_fwd_kernel<bf16_raw>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
+                       (const bf16_raw*)X, (bf16_raw*)Y, count, act, slope);
+  else
+    hipLaunchKernelGGL(act_fwd_kernel<float>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
+                       (const float*)X, (float*)Y, count, act, slope);
+  return launch_status();
+}
+
+int hfta_act_bwd(int64_t count, int dtype, const void* Z, const void* dY, void* dX, int act, float slope,
+                 int from_output, void* stream) {
+  if (count <= 0 || !valid_dtype(dtype) || !Z || !dY || !dX || !valid_act(act)) return HFTA_EINVAL;
+  if (from_output && (act == HFTA_ACT_GELU || (act == HFTA_ACT_LEAKY && !(slope > 0.f)))) return HFTA_EUNSUPPORTED;
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(act_bwd_kernel<bf16_raw>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
+                       (const bf16_raw*)Z, (const bf16_raw*)dY, (bf16_raw*)dX, count, act, slope, from_output);
+  else
+    hipLaunchKernelGGL(act_bwd_kernel<float>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
+                       (const float*)Z, (const float*)dY, (float*)dX, count, act, slope, from_output);
+  return launch_status();
+}
+
+int hfta_bias_act_nchw(int64_t Nb, int64_t K, int64_t HW, int dtype, void* Y, const void* bias, int act, float slope,
+                       void* stream) {
+  if (Nb <= 0 || K <= 0 || HW <= 0 || !valid_dtype(dtype) || !Y || !valid_act(act)) return HFTA_EINVAL;
+  const int64_t total = Nb * K * HW;
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(bias_act_nchw_kernel<bf16_raw>, dim3(stream_blocks(total)), dim3(256), 0, as_stream(stream),
+                       (bf16_raw*)Y, (const bf16_raw*)bias, K, HW, total, act, slope);
+  else
+    hipLaunchKernelGGL(bias_act_nchw_kernel<float>, dim3(stream_blocks(total)), dim3(256), 0, as_stream(stream),
+                       (float*)Y, (const float*)bias, K, HW, total, act, slope);
+  return launch_status();
+}
+
+int hfta_dropout(int64_t count, int dtype, const void* X, const uint8_t* mask, float p, void* Y, void* stream) {
+  if (count <= 0 || !valid_dtype(dtype) || !X || !mask || !Y || !(p >= 0.f) || !(p < 1.f)) return HFTA_EINVAL;
+  const float scale = 1.f / (1.f - p);
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(dropout_kernel<bf16_raw>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
+                       (const bf16_raw*)X, mask, (bf16_raw*)Y, count, scale);
+  else
+    hipLaunchKernelGGL(dropout_kernel<float>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
+                       (const float*)X, mask, (float*)Y, count, scale);
+  return launch_status();
+}
+
+int hfta_layernorm_fwd(int B, int R, int E, int dtype, const void* X, const float* w, const float* b, float eps,
+                       float* save_mean, float* save_invstd, void* Y, void* stream) {
+  if (B <= 0 || R <= 0 || E <= 0 || !valid_dtype(dtype) || !X || !w || !b || !save_mean || !save_invstd || !Y || !(eps >= 0.f))
+    return HFTA_EINVAL;
+  const int64_t rows = (int64_t)B * R;
+  if ((rows + 3) / 4 > 0x7fffffffLL) return HFTA_EINVAL;
+  dim3 grid((unsigned)((rows + 3) / 4));
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(layernorm_fwd_kernel<bf16_raw>, grid, dim3(256), 0, as_stream(stream), (const bf16_raw*)X, w, b, eps,
+                       save_mean, save_invstd, (bf16_raw*)Y, R, E, rows);
+  else
+    hipLaunchKernelGGL(layernorm_fwd_kernel<float>, grid, dim3(256), 0, as_stream(stream), (const float*)X, w, b, eps,
+                       save_mean, save_invstd, (float*)Y, R, E, rows);
+  return launch_status();
+}
+
+static int ln_blocks(int R) {
+  int nb = (R + 63) / 64;
+  return nb > 256 ? 256 : nb;
+}
+
+size_t hfta_layernorm_bwd_workspace_bytes(int B, int R, int E) {
+  if (B <= 0 || R <= 0 || E <= 0) return 0;
+  return (size_t)B * ln_blocks(R) * 2 * (size_t)E * sizeof(float);
+}
+
+int hfta_layernorm_bwd(int B, int R, int E, int dtype, const void* X, const void* dY, const float* w,
+                       const float* save_mean, const float* save_invstd, void* dX, float* dw, float* db,
+                       void* workspace, size_t ws_bytes, void* stream) {
+  if (B <= 0 || R <= 0 || E <= 0 || !valid_dtype(dtype) || !X || !dY || !w || !save_mean || !save_invstd || !dX || !dw || !db)
+    return HFTA_EINVAL;
+  if (B > 65535) return HFTA_EUNSUPPORTED;
+  if (!workspace || ws_bytes < hfta_layernorm_bwd_workspace_bytes(B, R, E)) return HFTA_EWORKSPACE;
+  const int nblk = ln_blocks(R);
+  const int rpb = (R + nblk - 1) / nblk;
+  hipStream_t st = as_stream(stream);
+  dim3 grid((unsigned)nblk, (unsigned)B);
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(layernorm_bwd_kernel<bf16_raw>, grid, dim3(256), 0, st, (const bf16_raw*)X, (const bf16_raw*)dY, w,
+                       save_mean, save_invstd, (bf16_raw*)dX, (float*)workspace, R, E, rpb);
+  else
+    hipLaunchKernelGGL(layernorm_bwd_kernel<float>, grid, dim3(256), 0, st, (const float*)X, (const float*)dY, w, save_mean,
+                       save_invstd, (float*)dX, (float*)workspace, R, E, rpb);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  hipLaunchKernelGGL(layernorm_bwd_reduce_kernel, dim3((unsigned)((E + 255) / 256), (unsigned)B), dim3(256), 0, st,
+                     (const float*)workspace, dw, db, E, nblk);
+  return launch_status();
+}
+
+int hfta_softmax_xent(int B, int R, int K, int dtype, const void* logits, const int32_t* labels, float* loss,
+                      void* dlogits, void* stream) {
+  if (B <= 0 || R <= 0 || K <= 0 || !valid_dtype(dtype) || !logits || !labels || !loss || !dlogits) return HFTA_EINVAL;
+  const int threads = R >= 1024 ? 1024 : ((R + 63) / 64) * 64;
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(softmax_xent_kernel<bf16_raw>, dim3((unsigned)B), dim3(threads), 0, as_stream(stream),
+                       (const bf16_raw*)logits, labels, loss, (bf16_raw*)dlogits, R, K);
+  else
+    hipLaunchKernelGGL(softmax_xent_kernel<float>, dim3((unsigned)B), dim3(threads), 0, as_stream(stream),
+                       (const float*)logits, labels, loss, (float*)dlogits, R, K);
+  return launch_status();
+}
+
+int hfta_bce_logits(int B, int64_t R, int dtype, const void* logits, const void* targets, float* loss, void* dlogits,
+                    void* stream) {
+  if (B <= 0 || R <= 0 || !valid_dtype(dtype) || !logits || !targets || !loss || !dlogits) return HFTA_EINVAL;
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL((pointwise_loss_kernel<bf16_raw, 0>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
+                       (const bf16_raw*)logits, (const bf16_raw*)targets, loss, (bf16_raw*)dlogits, R);
+  else
+    hipLaunchKernelGGL((pointwise_loss_kernel<float, 0>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
+                       (const float*)logits, (const float*)targets, loss, (float*)dlogits, R);
+  return launch_status();
+}
+
+int hfta_mse(int B, int64_t R, int dtype, const void* pred, const void* target, float* loss, void* dpred, void* stream) {
+  if (B <= 0 || R <= 0 || !valid_dtype(dtype) || !pred || !target || !loss || !dpred) return HFTA_EINVAL;
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL((pointwise_loss_kernel<bf16_raw, 1>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
+                       (const bf16_raw*)pred, (const bf16_raw*)target, loss, (bf16_raw*)dpred, R);
+  else
+    hipLaunchKernelGGL((pointwise_loss_kernel<float, 1>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
+                       (const float*)pred, (const float*)target, loss, (float*)dpred, R);
+  return launch_status();
+}
+
+}  // extern "C"

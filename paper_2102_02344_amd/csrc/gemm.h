@@ -1,0 +1,315 @@
+// Batched, strided GEMM core on the CDNA4 matrix cores.
+//
+// One kernel serves the three forms of the fused Linear and the fused k=1
+// Conv1d (forward, data gradient, weight gradient): every model of the array is
+// one slice of the batch, so B weight sets are one launch (the fusion rules
+// table's "baddbmm" / grouped-convolution rows).
+//
+//   C[g][m][n] = epilogue( sum_{s<S} sum_{k<K} A[g][s][m][k] * B[g][s][k][n] )
+//
+// g = (g0, g1) is a two-level batch index; s is an outer reduction index (the
+// sample axis of the k=1 convolution's weight gradient).  Each operand is
+// addressed by element strides and must be contiguous along exactly one of its
+// two matrix dims; C is contiguous along n.
+//
+// Tiling: 256 threads = 4 wavefronts compute a 128x128 tile of C; each wavefront
+// owns a 64x64 quadrant as 2x2 MFMA 32x32 blocks with fp32 accumulators.
+// Operand tiles are staged through LDS as [row][64 B of k + 16 B pad] so that a
+// lane's MFMA fragment (16 B along k) is one conflict-free ds_read_b128;
+// operands that are contiguous along m/n in memory are transposed in registers
+// on their way into LDS.  Global loads of tile t+1 are issued before the MFMAs
+// of tile t (register-staged double buffering, two LDS buffers, one barrier per
+// k-tile).
+#pragma once
+#include "common.h"
+
+namespace hfta {
+
+struct GemmDesc {
+  const void* A;
+  const void* Bm;
+  void* C;
+  int M, N, K, S;
+  int G0, G1;
+  int64_t a_ld, a_ss, a_g0, a_g1;  // a_ld: stride of A's non-contiguous matrix dim
+  int64_t b_ld, b_ss, b_g0, b_g1;
+  int64_t c_ld, c_g0, c_g1;
+  bool a_kc, b_kc;                 // operand contiguous along k (else along m / n)
+  const void* bias;                // storage dtype, or nullptr
+  int bias_mode;                   // 1: per row m, 2: per column n
+  int64_t bias_g0, bias_g1;
+  int act;
+  float slope;
+  int dtype;                       // storage type of A and B (and of C unless out_f32)
+  bool out_f32;
+  int splits;                      // > 1: fp32 partials [split][G0*G1][M][N] go to `partial`
+  float* partial;
+};
+
+struct GemmArgs {
+  const void* A;
+  const void* Bm;
+  void* C;
+  const void* bias;
+  float* partial;
+  int64_t a_ld, a_ss, a_g0, a_g1;
+  int64_t b_ld, b_ss, b_g0, b_g1;
+  int64_t c_ld, c_g0, c_g1;
+  int64_t bias_g0, bias_g1;
+  int M, N, K, S, G1;
+  int tiles_n, tiles_per_seg, total_tiles, splits;
+  int a_vec, b_vec;
+  int bias_mode, act;
+  float slope;
+};
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+constexpr int GEMM_BM = 128, GEMM_BN = 128, GEMM_THREADS = 256;
+constexpr int GEMM_PITCH = 80;                       // bytes per LDS row: 64 B of k + 16 B pad
+constexpr int GEMM_TILE_BYTES = 128 * GEMM_PITCH;    // one operand tile
+
+template <typename T> struct GemmT;
+template <> struct GemmT<bf16_raw> { static constexpr int KG = 8, BK = 32, NV = 4, KQ = 8; };
+template <> struct GemmT<float>    { static constexpr int KG = 4, BK = 16, NV = 2, KQ = 4; };
+
+// ---- global -> registers ------------------------------------------------
+// K-contiguous operand: thread t stages 16-byte group (t % 4) of rows t/4 and t/4 + 64.
+template <typename T>
+__device__ __forceinline__ void load_kc(uint4 (&q)[2], const T* base, int64_t ld, int row0, int rows,
+                                        int k0, int K, int vec, int t) {
+  constexpr int KG = GemmT<T>::KG;
+  const int g = t & 3;
+  const int k = k0 + g * KG;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int r = row0 + (t >> 2) + 64 * h;
+    const T* src = base + (int64_t)r * ld + k;
+    if (vec && r < rows && k + KG <= K) {
+      q[h] = *reinterpret_cast<const uint4*>(src);
+    } else {
+      T tmp[KG];
+#pragma unroll
+      for (int e = 0; e < KG; ++e) tmp[e] = (r < rows && k + e < K) ? src[e] : T(0);
+      q[h] = *reinterpret_cast<const uint4*>(tmp);
+    }
+  }
+}
+__device__ __forceinline__ void store_kc(unsigned char* tile, const uint4 (&q)[2], int t) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+    *reinterpret_cast<uint4*>(tile + ((t >> 2) + 64 * h) * GEMM_PITCH + (t & 3) * 16) = q[h];
+}
+
+// m/n-contiguous operand: thread t stages a 4(k) x NV(n) block: k-quad t % KQ, n-group t / KQ.
+template <typename T>
+__device__ __forceinline__ void load_nc(uint2 (&q)[4], const T* base, int64_t ld, int col0, int cols,
+                                        int k0, int K, int vec, int t) {
+  constexpr int NV = GemmT<T>::NV, KQ = GemmT<T>::KQ;
+  const int kq = t % KQ, ng = t / KQ;
+  const int c = col0 + ng * NV;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int k = k0 + 4 * kq + j;
+    const T* src = base + (int64_t)k * ld + c;
+    if (vec && k < K && c + NV <= cols) {
+      q[j] = *reinterpret_cast<const uint2*>(src);
+    } else {
+      T tmp[NV];
+#pragma unroll
+      for (int e = 0; e < NV; ++e) tmp[e] = (k < K && c + e < cols) ? src[e] : T(0);
+      q[j] = *reinterpret_cast<const uint2*>(tmp);
+    }
+  }
+}
+__device__ __forceinline__ void store_nc_bf16(unsigned char* tile, const uint2 (&q)[4], int t) {
+  const int kq = t % 8, ng = t / 8;
+  // q[j] = 4 bf16 along n for k = 4kq + j; emit 4 rows (n) of 4 bf16 along k
+  const uint32_t a0 = q[0].x, a1 = q[1].x, a2 = q[2].x, a3 = q[3].x;
+  const uint32_t b0 = q[0].y, b1 = q[1].y, b2 = q[2].y, b3 = q[3].y;
+  uint2 o[4];
+  o[0] = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
+  o[1] = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
+  o[2] = make_uint2((b0 & 0xffffu) | (b1 << 16), (b2 & 0xffffu) | (b3 << 16));
+  o[3] = make_uint2((b0 >> 16) | (b1 & 0xffff0000u), (b2 >> 16) | (b3 & 0xffff0000u));
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    *reinterpret_cast<uint2*>(tile + (ng * 4 + i) * GEMM_PITCH + kq * 8) = o[i];
+}
+__device__ __forceinline__ void store_nc_f32(unsigned char* tile, const uint2 (&q)[4], int t) {
+  const int kq = t % 4, ng = t / 4;
+  *reinterpret_cast<uint4*>(tile + (ng * 2 + 0) * GEMM_PITCH + kq * 16) = make_uint4(q[0].x, q[1].x, q[2].x, q[3].x);
+  *reinterpret_cast<uint4*>(tile + (ng * 2 + 1) * GEMM_PITCH + kq * 16) = make_uint4(q[0].y, q[1].y, q[2].y, q[3].y);
+}
+
+template <typename T, bool KC> struct Stager;
+template <typename T> struct Stager<T, true> {
+  uint4 q[2];
+  __device__ __forceinline__ void load(const T* base, int64_t ld, int r0, int rows, int k0, int K, int vec, int t) {
+    load_kc<T>(q, base, ld, r0, rows, k0, K, vec, t);
+  }
+  __device__ __forceinline__ void store(unsigned char* tile, int t) { store_kc(tile, q, t); }
+};
+template <> struct Stager<bf16_raw, false> {
+  uint2 q[4];
+  __device__ __forceinline__ void load(const bf16_raw* base, int64_t ld, int r0, int rows, int k0, int K, int vec, int t) {
+    load_nc<bf16_raw>(q, base, ld, r0, rows, k0, K, vec, t);
+  }
+  __device__ __forceinline__ void store(unsigned char* tile, int t) { store_nc_bf16(tile, q, t); }
+};
+template <> struct Stager<float, false> {
+  uint2 q[4];
+  __device__ __forceinline__ void load(const float* base, int64_t ld, int r0, int rows, int k0, int K, int vec, int t) {
+    load_nc<float>(q, base, ld, r0, rows, k0, K, vec, t);
+  }
+  __device__ __forceinline__ void store(unsigned char* tile, int t) { store_nc_f32(tile, q, t); }
+};
+
+// ---- MFMA on one k-tile ---------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void mma_tile(f32x16_t (&acc)[2][2], const unsigned char* As,
+                                         const unsigned char* Bs, int wm, int wn, int lane);
+template <>
+__device__ __forceinline__ void mma_tile<bf16_raw>(f32x16_t (&acc)[2][2], const unsigned char* As,
+                                                   const unsigned char* Bs, int wm, int wn, int lane) {
+  const int r = lane & 31, gsel = lane >> 5;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    bf16x8_t a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      a[i] = *reinterpret_cast<const bf16x8_t*>(As + (wm * 64 + i * 32 + r) * GEMM_PITCH + (2 * s + gsel) * 16);
+      b[i] = *reinterpret_cast<const bf16x8_t*>(Bs + (wn * 64 + i * 32 + r) * GEMM_PITCH + (2 * s + gsel) * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+}
+template <>
+__device__ __forceinline__ void mma_tile<float>(f32x16_t (&acc)[2][2], const unsigned char* As,
+                                                const unsigned char* Bs, int wm, int wn, int lane) {
+  const int r = lane & 31, gsel = lane >> 5;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    float4 a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      a[i] = *reinterpret_cast<const float4*>(As + (wm * 64 + i * 32 + r) * GEMM_PITCH + (2 * s + gsel) * 16);
+      b[i] = *reinterpret_cast<const float4*>(Bs + (wn * 64 + i * 32 + r) * GEMM_PITCH + (2 * s + gsel) * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
+      }
+  }
+}
+
+// ---- the kernel -----------------------------------------------------------
+template <typename T, bool A_KC, bool B_KC, typename OutT>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs p) {
+  constexpr int BK = GemmT<T>::BK;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][GEMM_TILE_BYTES];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  const int m0 = tile_m * GEMM_BM, n0 = tile_n * GEMM_BN;
+  const int split = blockIdx.z % p.splits, g = blockIdx.z / p.splits;
+  const int g0 = g / p.G1, g1 = g % p.G1;
+
+  const T* Ab = reinterpret_cast<const T*>(p.A) + g0 * p.a_g0 + g1 * p.a_g1;
+  const T* Bb = reinterpret_cast<const T*>(p.Bm) + g0 * p.b_g0 + g1 * p.b_g1;
+
+  const int t_begin = (int)((int64_t)p.total_tiles * split / p.splits);
+  const int t_end = (int)((int64_t)p.total_tiles * (split + 1) / p.splits);
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  Stager<T, A_KC> sa;
+  Stager<T, B_KC> sb;
+  auto issue = [&](int tt) {
+    const int seg = tt / p.tiles_per_seg;
+    const int k0 = (tt - seg * p.tiles_per_seg) * BK;
+    sa.load(Ab + seg * p.a_ss, p.a_ld, m0, p.M, k0, p.K, p.a_vec, t);
+    sb.load(Bb + seg * p.b_ss, p.b_ld, n0, p.N, k0, p.K, p.b_vec, t);
+  };
+
+  if (t_begin < t_end) {
+    issue(t_begin);
+    sa.store(smem[0][0], t);
+    sb.store(smem[0][1], t);
+    __syncthreads();
+    int buf = 0;
+    for (int tt = t_begin; tt < t_end; ++tt) {
+      const bool more = tt + 1 < t_end;
+      if (more) issue(tt + 1);
+      mma_tile<T>(acc, smem[buf][0], smem[buf][1], wm, wn, lane);
+      if (more) {
+        sa.store(smem[buf ^ 1][0], t);
+        sb.store(smem[buf ^ 1][1], t);
+      }
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+
+  // epilogue: lane holds column (lane % 32) and rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 block
+  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  if (p.splits > 1) {
+    float* Pb = p.partial + ((int64_t)split * gridDim.z / p.splits + g) * (int64_t)p.M * p.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn * 64 + j * 32 + col_l;
+        if (n >= p.N) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+          if (m < p.M) Pb[(int64_t)m * p.N + n] = acc[i][j][v];
+        }
+      }
+    return;
+  }
+  OutT* Cb = reinterpret_cast<OutT*>(p.C) + g0 * p.c_g0 + g1 * p.c_g1;
+  const T* bias = p.bias ? reinterpret_cast<const T*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn * 64 + j * 32 + col_l;
+      if (n >= p.N) continue;
+      float bn = 0.f;
+      if (bias && p.bias_mode == 2) bn = Elem<T>::load(bias + n);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+        if (m >= p.M) continue;
+        float x = acc[i][j][v] + bn;
+        if (bias && p.bias_mode == 1) x += Elem<T>::load(bias + m);
+        x = apply_act(x, p.act, p.slope);
+        Elem<OutT>::store(Cb + (int64_t)m * p.c_ld + n, x);
+      }
+    }
+}
+
+int gemm_pick_splits(const GemmDesc& d);
+size_t gemm_partial_bytes(const GemmDesc& d, int splits);
+int gemm_launch(const GemmDesc& d, hipStream_t stream);
+
+}  // namespace hfta

@@ -1,0 +1,103 @@
+// Host side of the batched GEMM core: split selection, alignment checks, dispatch.
+#include "gemm.h"
+
+namespace hfta {
+
+// Sum split-K partials in a fixed order: out[i] = sum_s partial[s][i].
+__global__ void splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out,
+                                     int64_t count, int splits) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  float s = 0.f;
+  for (int k = 0; k < splits; ++k) s += partial[(int64_t)k * count + i];
+  out[i] = s;
+}
+
+static inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+static int total_tiles(const GemmDesc& d) {
+  const int BK = d.dtype == HFTA_BF16 ? GemmT<bf16_raw>::BK : GemmT<float>::BK;
+  return d.S * ((d.K + BK - 1) / BK);
+}
+
+// Enough workgroups to fill 256 compute units a few times over, without cutting
+// the reduction into pieces shorter than 8 k-tiles.
+int gemm_pick_splits(const GemmDesc& d) {
+  const int64_t tiles = (int64_t)((d.M + GEMM_BM - 1) / GEMM_BM) * ((d.N + GEMM_BN - 1) / GEMM_BN) * d.G0 * d.G1;
+  const int tt = total_tiles(d);
+  if (tiles >= 512 || tt < 16) return 1;
+  int64_t want = (1024 + tiles - 1) / tiles;
+  int64_t cap = tt / 8;
+  if (want > cap) want = cap;
+  if (want > 256) want = 256;
+  return want < 1 ? 1 : (int)want;
+}
+
+size_t gemm_partial_bytes(const GemmDesc& d, int splits) {
+  if (splits <= 1) return 0;
+  return (size_t)splits * d.G0 * d.G1 * (size_t)d.M * d.N * sizeof(float);
+}
+
+template <typename T, bool A_KC, bool B_KC>
+static void launch_typed(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t st) {
+  if (d.out_f32 || d.splits > 1)
+    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, float>), grid, dim3(GEMM_THREADS), 0, st, a);
+  else
+    hipLaunchKernelGGL((gemm_kernel<T, A_KC, B_KC, T>), grid, dim3(GEMM_THREADS), 0, st, a);
+}
+
+template <typename T>
+static int launch_layout(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t st) {
+  if (d.a_kc && !d.b_kc) launch_typed<T, true, false>(d, a, grid, st);
+  else if (d.a_kc && d.b_kc) launch_typed<T, true, true>(d, a, grid, st);
+  else if (!d.a_kc && !d.b_kc) launch_typed<T, false, false>(d, a, grid, st);
+  else return HFTA_EUNSUPPORTED;
+  return launch_status();
+}
+
+int gemm_launch(const GemmDesc& d, hipStream_t st) {
+  if (d.M <= 0 || d.N <= 0 || d.K <= 0 || d.S <= 0 || d.G0 <= 0 || d.G1 <= 0) return HFTA_EINVAL;
+  const int64_t G = (int64_t)d.G0 * d.G1;
+  const int splits = d.splits < 1 ? 1 : d.splits;
+  if (G * splits > 65535) return HFTA_EUNSUPPORTED;
+  if (splits > 1 && (!d.partial || !d.out_f32 || d.bias || d.act != HFTA_ACT_NONE)) return HFTA_EINVAL;
+
+  GemmArgs a;
+  a.A = d.A; a.Bm = d.Bm; a.C = d.C; a.bias = d.bias; a.partial = d.partial;
+  a.a_ld = d.a_ld; a.a_ss = d.a_ss; a.a_g0 = d.a_g0; a.a_g1 = d.a_g1;
+  a.b_ld = d.b_ld; a.b_ss = d.b_ss; a.b_g0 = d.b_g0; a.b_g1 = d.b_g1;
+  a.c_ld = d.c_ld; a.c_g0 = d.c_g0; a.c_g1 = d.c_g1;
+  a.bias_g0 = d.bias_g0; a.bias_g1 = d.bias_g1;
+  a.M = d.M; a.N = d.N; a.K = d.K; a.S = d.S; a.G1 = d.G1;
+  a.tiles_n = (d.N + GEMM_BN - 1) / GEMM_BN;
+  const int BK = d.dtype == HFTA_BF16 ? GemmT<bf16_raw>::BK : GemmT<float>::BK;
+  a.tiles_per_seg = (d.K + BK - 1) / BK;
+  a.total_tiles = d.S * a.tiles_per_seg;
+  a.splits = splits;
+  a.bias_mode = d.bias ? d.bias_mode : 0;
+  a.act = d.act; a.slope = d.slope;
+
+  // vector-load eligibility: every address the fast path forms must be aligned
+  const int es = (int)dtype_size(d.dtype);
+  const int kg = 16 / es, nv = 8 / es;
+  auto ok = [&](const void* p, int64_t ld, int64_t ss, int64_t s0, int64_t s1, bool kc) {
+    const int q = kc ? kg : nv;
+    return aligned_to(p, kc ? 16 : 8) && ld % q == 0 && ss % q == 0 && s0 % q == 0 && s1 % q == 0;
+  };
+  a.a_vec = ok(d.A, d.a_ld, d.a_ss, d.a_g0, d.a_g1, d.a_kc);
+  a.b_vec = ok(d.Bm, d.b_ld, d.b_ss, d.b_g0, d.b_g1, d.b_kc);
+
+  const int tiles_m = (d.M + GEMM_BM - 1) / GEMM_BM;
+  dim3 grid((unsigned)(tiles_m * a.tiles_n), 1, (unsigned)(G * splits));
+  int rc = d.dtype == HFTA_BF16 ? launch_layout<bf16_raw>(d, a, grid, st) : launch_layout<float>(d, a, grid, st);
+  if (rc != HFTA_OK) return rc;
+  if (splits > 1) {
+    const int64_t count = G * (int64_t)d.M * d.N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+                       d.partial, reinterpret_cast<float*>(d.C), count, splits);
+    return launch_status();
+  }
+  return HFTA_OK;
+}
+
+}  // namespace hfta

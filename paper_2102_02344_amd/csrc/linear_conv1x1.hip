@@ -1,0 +1,222 @@
+// Fused Linear and fused k=1 Conv1d: argument checking and mapping of the
+// forward / data-gradient / weight-gradient forms onto the batched GEMM core,
+// plus the bias-gradient reductions.
+#include "gemm.h"
+
+using namespace hfta;
+
+namespace {
+
+// dbias of the fused Linear: column sums of dY[b] ([M][Fy]); 64 columns x 4 row slices per block.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ dY, float* __restrict__ out,
+                                                    int M, int Fy) {
+  __shared__ float part[4][64];
+  const int b = blockIdx.y;
+  const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int slice = threadIdx.x >> 6;
+  float s = 0.f;
+  if (col < Fy) {
+    const T* p = dY + (int64_t)b * M * Fy + col;
+    for (int r = slice; r < M; r += 4) s += Elem<T>::load(p + (int64_t)r * Fy);
+  }
+  part[slice][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (slice == 0 && col < Fy)
+    out[(int64_t)b * Fy + col] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+}
+
+// dbias of the fused conv: sum over (n, l) of dY[b, n, o, :]; one workgroup per (o, b).
+template <typename T>
+__global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ dY, float* __restrict__ out,
+                                                    int Nb, int Co, int L, int64_t sb, int64_t sn, int64_t sc) {
+  __shared__ float part[4];
+  const int o = blockIdx.x, b = blockIdx.y;
+  const T* base = dY + b * sb + o * sc;
+  float s = 0.f;
+  const int64_t total = (int64_t)Nb * L;
+  for (int64_t i = threadIdx.x; i < total; i += 256) {
+    const int n = (int)(i / L), l = (int)(i - (int64_t)n * L);
+    s += Elem<T>::load(base + n * sn + l);
+  }
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) out[(int64_t)b * Co + o] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+bool fits_i32(int64_t v) { return v > 0 && v <= 0x7fffffffLL; }
+
+GemmDesc base_desc(int dtype) {
+  GemmDesc d{};
+  d.S = 1; d.G0 = 1; d.G1 = 1;
+  d.act = HFTA_ACT_NONE; d.slope = 0.f;
+  d.dtype = dtype; d.out_f32 = false; d.splits = 1; d.partial = nullptr;
+  d.bias = nullptr; d.bias_mode = 0;
+  return d;
+}
+
+GemmDesc linear_dw_desc(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* dY, float* dW) {
+  GemmDesc d = base_desc(dtype);
+  d.A = X; d.Bm = dY; d.C = dW;
+  d.M = Fx; d.N = Fy; d.K = M; d.G0 = B;
+  d.a_kc = false; d.a_ld = Fx; d.a_g0 = (int64_t)M * Fx;      // A[m=fx][k=row] = X[row][fx]
+  d.b_kc = false; d.b_ld = Fy; d.b_g0 = (int64_t)M * Fy;
+  d.c_ld = Fy; d.c_g0 = (int64_t)Fx * Fy;
+  d.out_f32 = true;
+  return d;
+}
+
+GemmDesc conv_dw_desc(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t* xs,
+                      const void* dY, const int64_t* dys, float* dW) {
+  GemmDesc d = base_desc(dtype);
+  d.A = dY; d.Bm = X; d.C = dW;
+  d.M = Co; d.N = Ci; d.K = L; d.S = Nb; d.G0 = B;
+  d.a_kc = true; d.a_ld = dys[2]; d.a_ss = dys[1]; d.a_g0 = dys[0];
+  d.b_kc = true; d.b_ld = xs[2]; d.b_ss = xs[1]; d.b_g0 = xs[0];   // B[k=l][n=c] = X[c][l]
+  d.c_ld = Ci; d.c_g0 = (int64_t)Co * Ci;
+  d.out_f32 = true;
+  return d;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hfta_linear_fwd(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* W, const void* bias,
+                    void* Y, int act, float act_slope, void* stream) {
+  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !X || !W || !Y || !valid_dtype(dtype) || !valid_act(act))
+    return HFTA_EINVAL;
+  if (!fits_i32((int64_t)M * Fx) || !fits_i32((int64_t)M * Fy) || !fits_i32((int64_t)Fx * Fy)) return HFTA_EINVAL;
+  GemmDesc d = base_desc(dtype);
+  d.A = X; d.Bm = W; d.C = Y;
+  d.M = M; d.N = Fy; d.K = Fx; d.G0 = B;
+  d.a_kc = true; d.a_ld = Fx; d.a_g0 = (int64_t)M * Fx;
+  d.b_kc = false; d.b_ld = Fy; d.b_g0 = (int64_t)Fx * Fy;
+  d.c_ld = Fy; d.c_g0 = (int64_t)M * Fy;
+  d.bias = bias; d.bias_mode = 2; d.bias_g0 = Fy;
+  d.act = act; d.slope = act_slope;
+  return gemm_launch(d, as_stream(stream));
+}
+
+size_t hfta_linear_bwd_workspace_bytes(int B, int M, int Fx, int Fy, int dtype) {
+  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !valid_dtype(dtype)) return 0;
+  GemmDesc d = linear_dw_desc(B, M, Fx, Fy, dtype, nullptr, nullptr, nullptr);
+  return gemm_partial_bytes(d, gemm_pick_splits(d));
+}
+
+int hfta_linear_bwd(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* W, const void* dY,
+                    void* dX, float* dW, float* dbias, void* workspace, size_t ws_bytes, void* stream) {
+  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !dY || !valid_dtype(dtype)) return HFTA_EINVAL;
+  if ((dX && !W) || (dW && !X)) return HFTA_EINVAL;
+  if (!fits_i32((int64_t)M * Fx) || !fits_i32((int64_t)M * Fy) || !fits_i32((int64_t)Fx * Fy)) return HFTA_EINVAL;
+  hipStream_t st = as_stream(stream);
+  GemmDesc dw = linear_dw_desc(B, M, Fx, Fy, dtype, X, dY, dW);
+  if (dW) {
+    dw.splits = gemm_pick_splits(dw);
+    const size_t need = gemm_partial_bytes(dw, dw.splits);
+    if (need > 0 && (!workspace || ws_bytes < need)) return HFTA_EWORKSPACE;
+    dw.partial = reinterpret_cast<float*>(workspace);
+  }
+  if (dX) {
+    GemmDesc d = base_desc(dtype);
+    d.A = dY; d.Bm = W; d.C = dX;
+    d.M = M; d.N = Fx; d.K = Fy; d.G0 = B;
+    d.a_kc = true; d.a_ld = Fy; d.a_g0 = (int64_t)M * Fy;
+    d.b_kc = true; d.b_ld = Fy; d.b_g0 = (int64_t)Fx * Fy;    // B[k=fy][n=fx] = W[fx][fy]
+    d.c_ld = Fx; d.c_g0 = (int64_t)M * Fx;
+    int rc = gemm_launch(d, st);
+    if (rc != HFTA_OK) return rc;
+  }
+  if (dW) {
+    int rc = gemm_launch(dw, st);
+    if (rc != HFTA_OK) return rc;
+  }
+  if (dbias) {
+    dim3 grid((unsigned)((Fy + 63) / 64), (unsigned)B);
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(colsum_kernel<bf16_raw>, grid, dim3(256), 0, st, (const bf16_raw*)dY, dbias, M, Fy);
+    else
+      hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)dY, dbias, M, Fy);
+    return launch_status();
+  }
+  return HFTA_OK;
+}
+
+static int check_conv1x1(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype)) return HFTA_EINVAL;
+  if (!fits_i32((int64_t)Ci * L) || !fits_i32((int64_t)Co * L) || !fits_i32((int64_t)Co * Ci)) return HFTA_EINVAL;
+  if ((int64_t)B * Nb > 65535) return HFTA_EUNSUPPORTED;
+  return HFTA_OK;
+}
+
+int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                     const void* W, const void* bias, void* Y, const int64_t ys[4], int act, float act_slope,
+                     void* stream) {
+  int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
+  if (rc != HFTA_OK) return rc;
+  if (!X || !W || !Y || !xs || !ys || !valid_act(act)) return HFTA_EINVAL;
+  if (xs[3] != 1 || ys[3] != 1) return HFTA_EUNSUPPORTED;
+  GemmDesc d = base_desc(dtype);
+  d.A = W; d.Bm = X; d.C = Y;
+  d.M = Co; d.N = L; d.K = Ci; d.G0 = B; d.G1 = Nb;
+  d.a_kc = true; d.a_ld = Ci; d.a_g0 = (int64_t)Co * Ci; d.a_g1 = 0;
+  d.b_kc = false; d.b_ld = xs[2]; d.b_g0 = xs[0]; d.b_g1 = xs[1];
+  d.c_ld = ys[2]; d.c_g0 = ys[0]; d.c_g1 = ys[1];
+  d.bias = bias; d.bias_mode = 1; d.bias_g0 = Co; d.bias_g1 = 0;
+  d.act = act; d.slope = act_slope;
+  return gemm_launch(d, as_stream(stream));
+}
+
+size_t hfta_conv1x1_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  if (check_conv1x1(B, Nb, Ci, Co, L, dtype) != HFTA_OK) return 0;
+  const int64_t unit[4] = {(int64_t)Ci * L, (int64_t)B * Ci * L, L, 1};
+  GemmDesc d = conv_dw_desc(B, Nb, Ci, Co, L, dtype, nullptr, unit, nullptr, unit, nullptr);
+  return gemm_partial_bytes(d, gemm_pick_splits(d));
+}
+
+int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                     const void* W, const void* dY, const int64_t dys[4], void* dX, const int64_t dxs[4],
+                     float* dW, float* dbias, void* workspace, size_t ws_bytes, void* stream) {
+  int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
+  if (rc != HFTA_OK) return rc;
+  if (!dY || !dys) return HFTA_EINVAL;
+  if ((dX && (!W || !dxs)) || (dW && (!X || !xs))) return HFTA_EINVAL;
+  if (dys[3] != 1 || (dX && dxs[3] != 1) || (dW && xs[3] != 1)) return HFTA_EUNSUPPORTED;
+  hipStream_t st = as_stream(stream);
+  GemmDesc dw{};
+  if (dW) {
+    dw = conv_dw_desc(B, Nb, Ci, Co, L, dtype, X, xs, dY, dys, dW);
+    dw.splits = gemm_pick_splits(dw);
+    const size_t need = gemm_partial_bytes(dw, dw.splits);
+    if (need > 0 && (!workspace || ws_bytes < need)) return HFTA_EWORKSPACE;
+    dw.partial = reinterpret_cast<float*>(workspace);
+  }
+  if (dX) {
+    GemmDesc d = base_desc(dtype);
+    d.A = W; d.Bm = dY; d.C = dX;
+    d.M = Ci; d.N = L; d.K = Co; d.G0 = B; d.G1 = Nb;
+    d.a_kc = false; d.a_ld = Ci; d.a_g0 = (int64_t)Co * Ci; d.a_g1 = 0;   // A[m=c][k=o] = W[o][c]
+    d.b_kc = false; d.b_ld = dys[2]; d.b_g0 = dys[0]; d.b_g1 = dys[1];
+    d.c_ld = dxs[2]; d.c_g0 = dxs[0]; d.c_g1 = dxs[1];
+    rc = gemm_launch(d, st);
+    if (rc != HFTA_OK) return rc;
+  }
+  if (dW) {
+    rc = gemm_launch(dw, st);
+    if (rc != HFTA_OK) return rc;
+  }
+  if (dbias) {
+    dim3 grid((unsigned)Co, (unsigned)B);
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(rowsum_kernel<bf16_raw>, grid, dim3(256), 0, st, (const bf16_raw*)dY, dbias, Nb, Co, L,
+                         dys[0], dys[1], dys[2]);
+    else
+      hipLaunchKernelGGL(rowsum_kernel<float>, grid, dim3(256), 0, st, (const float*)dY, dbias, Nb, Co, L,
+                         dys[0], dys[1], dys[2]);
+    return launch_status();
+  }
+  return HFTA_OK;
+}
+
+}  // extern "C"

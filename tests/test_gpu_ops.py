@@ -1,0 +1,367 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by
+element, on the same seeded inputs.  Sizes span several 128x128 tiles plus a
+ragged tail; both storage dtypes.  Index outputs must match bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import hfta_inputs as hi
+from oracle import array as oa
+from oracle import ops as oops
+from util import DT, TDT, TOL, check, conv_strides, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2102_02344_amd import binding
+    return binding
+
+
+def empty(shape, dtype):
+    return torch.empty(shape, dtype=TDT[dtype] if isinstance(dtype, str) else dtype, device="cuda")
+
+
+def f32_tol(dtype):
+    """fp32 outputs (parameter gradients, statistics) accumulate in fp32 from exactly
+    representable inputs; hold them to a tighter bound than the bf16 storage tolerance."""
+    return 1e-5 if dtype == "f32" else 2e-4
+
+
+# ------------------------------------------------------------------ linear
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,M,Fx,Fy", [(3, 300, 200, 260), (2, 5, 1024, 16), (1, 129, 7, 3), (4, 32, 256, 512)])
+def test_linear_fwd_bwd(hb, dtype, B, M, Fx, Fy):
+    print(f"linear {dtype} B={B} M={M} Fx={Fx} Fy={Fy}", flush=True)
+    x = hi.normal(1, (B, M, Fx), dtype)
+    w = hi.normal(2, (B, Fx, Fy), dtype, 1.0 / np.sqrt(Fx))
+    b = hi.normal(3, (B, Fy), dtype)
+    dy = hi.normal(4, (B, M, Fy), dtype)
+    X, W, Bi, dY = dev(x, dtype), dev(w, dtype), dev(b, dtype), dev(dy, dtype)
+    Y = empty((B, M, Fy), dtype)
+    hb.linear_fwd(B, M, Fx, Fy, DT[dtype], X, W, Bi, Y)
+    check(host(Y), oa.linear_fwd(B, x, w, b), TOL[dtype], "Y")
+    # fused activation epilogue
+    hb.linear_fwd(B, M, Fx, Fy, DT[dtype], X, W, Bi, Y, hb.ACT_RELU)
+    check(host(Y), oops.act_fwd(oa.linear_fwd(B, x, w, b), oops.ACT_RELU), TOL[dtype], "relu(Y)")
+    hb.linear_fwd(B, M, Fx, Fy, DT[dtype], X, W, None, Y, hb.ACT_GELU)
+    check(host(Y), oops.act_fwd(oa.linear_fwd(B, x, w, None), oops.ACT_GELU), TOL[dtype], "gelu(Y)")
+    dX = empty((B, M, Fx), dtype)
+    dW = empty((B, Fx, Fy), torch.float32)
+    db = empty((B, Fy), torch.float32)
+    nws = hb.linear_bwd_workspace_bytes(B, M, Fx, Fy, DT[dtype])
+    ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
+    hb.linear_bwd(B, M, Fx, Fy, DT[dtype], X, W, dY, dX, dW, db, ws)
+    rdx, rdw, rdb = oa.linear_bwd(B, x, w, dy)
+    check(host(dX), rdx, TOL[dtype], "dX")
+    check(host(dW), rdw, f32_tol(dtype), "dW")
+    check(host(db), rdb, f32_tol(dtype), "dbias")
+
+
+def test_linear_identity_and_B1(hb):
+    # identity weights return X + bias exactly; B = 1 equals model 0 of a B = 2 call
+    B, M, F = 2, 70, 96
+    x = hi.normal(5, (B, M, F))
+    w = np.stack([np.eye(F, dtype=np.float32)] * B)
+    b = hi.normal(6, (B, F))
+    X, W, Bi = dev(x), dev(w), dev(b)
+    Y = empty((B, M, F), "f32")
+    hb.linear_fwd(B, M, F, F, 0, X, W, Bi, Y)
+    assert np.array_equal(host(Y), (x + b[:, None, :]).astype(np.float32).astype(np.float64))
+    w2 = hi.normal(7, (B, F, F))
+    W2 = dev(w2)
+    hb.linear_fwd(B, M, F, F, 0, X, W2, Bi, Y)
+    Y1 = empty((1, M, F), "f32")
+    hb.linear_fwd(1, M, F, F, 0, X[:1].contiguous(), W2[:1].contiguous(), Bi[:1].contiguous(), Y1)
+    assert torch.equal(Y1[0], Y[0])
+
+
+# ------------------------------------------------------------------ conv1x1
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,Ci,Co,L", [(3, 2, 70, 150, 300), (2, 3, 3, 64, 250), (2, 2, 128, 40, 129),
+                                          (2, 4, 64, 64, 500)])
+def test_conv1x1_fwd_bwd(hb, dtype, B, Nb, Ci, Co, L):
+    print(f"conv1x1 {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} L={L}", flush=True)
+    x = hi.normal(11, (Nb, B * Ci, L), dtype)
+    w = hi.normal(12, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    b = hi.normal(13, (B * Co,), dtype)
+    dy = hi.normal(14, (Nb, B * Co, L), dtype)
+    X, W, Bi, dY = dev(x, dtype), dev(w, dtype), dev(b, dtype), dev(dy, dtype)
+    xs, ys = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    Y = empty((Nb, B * Co, L), dtype)
+    hb.conv1x1_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Bi, Y, ys)
+    check(host(Y), oa.conv1x1_fwd(B, x, w, b), TOL[dtype], "Y")
+    dX = empty((Nb, B * Ci, L), dtype)
+    dW = empty((B * Co, Ci), torch.float32)
+    db = empty((B * Co,), torch.float32)
+    nws = hb.conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype])
+    ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
+    hb.conv1x1_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, dY, ys, dX, xs, dW, db, ws)
+    rdx, rdw, rdb = oa.conv1x1_bwd(B, x, w, dy)
+    check(host(dX), rdx, TOL[dtype], "dX")
+    check(host(dW), rdw, f32_tol(dtype), "dW")
+    check(host(db), rdb, f32_tol(dtype), "dbias")
+    # bit-reproducible (fixed-order split reduction, no atomics)
+    dW2 = empty((B * Co, Ci), torch.float32)
+    hb.conv1x1_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, dY, ys, None, None, dW2, None, ws)
+    assert torch.equal(dW, dW2)
+
+
+def test_conv1x1_cross_talk_and_linear_special_case(hb):
+    B, Nb, Ci, Co, L = 3, 2, 32, 48, 140
+    x = hi.normal(15, (Nb, B * Ci, L))
+    w = hi.normal(16, (B * Co, Ci))
+    X, W = dev(x), dev(w)
+    xs, ys = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    Y = empty((Nb, B * Co, L), "f32")
+    hb.conv1x1_fwd(B, Nb, Ci, Co, L, 0, X, xs, W, None, Y, ys)
+    # perturbing model 2's input and weights leaves models 0 and 1 bit-identical
+    x2 = x.copy(); x2[:, 2 * Ci:] += 1.0
+    w2 = w.copy(); w2[2 * Co:] *= 2.0
+    Y2 = empty((Nb, B * Co, L), "f32")
+    hb.conv1x1_fwd(B, Nb, Ci, Co, L, 0, dev(x2), xs, dev(w2), None, Y2, ys)
+    assert torch.equal(Y[:, :2 * Co], Y2[:, :2 * Co]) and not torch.equal(Y[:, 2 * Co:], Y2[:, 2 * Co:])
+    # L = 1 is the fused Linear with the weight transposed
+    x1 = hi.normal(17, (Nb, B * Ci, 1))
+    Yc = empty((Nb, B * Co, 1), "f32")
+    hb.conv1x1_fwd(B, Nb, Ci, Co, 1, 0, dev(x1), conv_strides(B, Ci, 1), W, None, Yc, conv_strides(B, Co, 1))
+    xl = np.ascontiguousarray(x1.reshape(Nb, B, Ci).transpose(1, 0, 2))
+    wl = np.ascontiguousarray(w.reshape(B, Co, Ci).transpose(0, 2, 1))
+    Yl = empty((B, Nb, Co), "f32")
+    hb.linear_fwd(B, Nb, Ci, Co, 0, dev(xl), dev(wl), None, Yl)
+    check(host(Yc).reshape(Nb, B, Co).transpose(1, 0, 2), host(Yl), 1e-6, "conv(L=1) vs linear")
+
+
+# ------------------------------------------------------------------ BatchNorm
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,C,L,act", [(3, 4, 5, 300, 1), (2, 3, 7, 250, 0), (2, 2, 64, 131, 2), (2, 8, 3, 1024, 1)])
+def test_bn_conv_layout(hb, dtype, B, Nb, C, L, act):
+    print(f"bn conv {dtype} B={B} Nb={Nb} C={C} L={L} act={act}", flush=True)
+    x = hi.snap(hi.normal(21, (Nb, B * C, L)) * 2.0 + 3.0, dtype)
+    g = (hi.normal(22, (B * C,)) * 0.5 + 1.0).astype(np.float32)
+    bt = hi.normal(23, (B * C,)) * 0.3
+    rm, rv = hi.normal(24, (B * C,)), np.abs(hi.normal(25, (B * C,))) + 0.5
+    dy = hi.normal(26, (Nb, B * C, L), dtype)
+    s = conv_strides(B, C, L)
+    X, dY = dev(x, dtype), dev(dy, dtype)
+    G, Bt, RM, RV = dev(g), dev(bt), dev(rm), dev(rv)
+    SM, SI = empty((B * C,), torch.float32), empty((B * C,), torch.float32)
+    Y = empty(x.shape, dtype)
+    hb.bn_fwd(B, Nb, C, L, DT[dtype], X, s, G, Bt, 1e-5, 0.1, RM, RV, SM, SI, Y, s, act, 0.2)
+    ry, rmean, rinv, nrm, nrv = oa.bn_fwd(B, x, g, bt, 1e-5, 0.1, rm, rv)
+    oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
+    check(host(Y), oops.act_fwd(ry, oact, 0.2), TOL[dtype], "Y")
+    check(host(SM), rmean, 1e-5, "mean")
+    check(host(SI), rinv, 1e-5, "invstd")
+    check(host(RM), nrm, 1e-5, "running_mean")
+    check(host(RV), nrv, 1e-5, "running_var")
+    dX = empty(x.shape, dtype)
+    dG, dB = empty((B * C,), torch.float32), empty((B * C,), torch.float32)
+    hb.bn_bwd(B, Nb, C, L, DT[dtype], X, s, dY, s, G, Bt, SM, SI, dX, s, dG, dB, act, 0.2)
+    # the oracle takes the activation mask from its own float64 pre-activation; elements whose
+    # pre-activation is within rounding of zero may legitimately take the other branch in fp32
+    knife = np.abs(ry) < 1e-5 * (np.abs(ry - bt[None, :, None]) + np.abs(bt)[None, :, None])
+    assert knife.sum() == 0, "regenerate inputs: pre-activation on the kink"
+    gdy = oops.act_bwd(ry, dy, oact, 0.2)
+    rdx, rdg, rdb = oa.bn_bwd(B, x, gdy, g, rmean, rinv)
+    check(host(dX), rdx, TOL[dtype], "dX")
+    check(host(dG), rdg, f32_tol(dtype), "dgamma")
+    check(host(dB), rdb, f32_tol(dtype), "dbeta")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bn_linear_layout_and_independence(hb, dtype):
+    B, Nb, C = 3, 32, 300
+    x = hi.snap(hi.normal(31, (B, Nb, C)) * 1.5 - 0.7, dtype)
+    g, bt = (hi.normal(32, (B, C)) * 0.5 + 1.0), hi.normal(33, (B, C)) * 0.3
+    dy = hi.normal(34, (B, Nb, C), dtype)
+    s = (Nb * C, C, 1, 1)
+    X, dY, G, Bt = dev(x, dtype), dev(dy, dtype), dev(g), dev(bt)
+    SM, SI = empty((B, C), torch.float32), empty((B, C), torch.float32)
+    Y = empty(x.shape, dtype)
+    hb.bn_fwd(B, Nb, C, 1, DT[dtype], X, s, G, Bt, 1e-5, 0.1, None, None, SM, SI, Y, s, hb.ACT_RELU, 0.0)
+    ry, rmean, rinv, _, _ = oa.bn_fwd(B, x, g, bt, 1e-5, 0.1, None, None, "linear")
+    check(host(Y), oops.act_fwd(ry, oops.ACT_RELU), TOL[dtype], "Y")
+    check(host(SM).reshape(-1), rmean, 1e-5, "mean")
+    dX = empty(x.shape, dtype)
+    dG, dB = empty((B, C), torch.float32), empty((B, C), torch.float32)
+    hb.bn_bwd(B, Nb, C, 1, DT[dtype], X, s, dY, s, G, Bt, SM, SI, dX, s, dG, dB, hb.ACT_RELU, 0.0)
+    rdx, rdg, rdb = oa.bn_bwd(B, x, oops.act_bwd(ry, dy, oops.ACT_RELU), g, rmean, rinv, "linear")
+    check(host(dX), rdx, TOL[dtype], "dX")
+    check(host(dG).reshape(-1), rdg, f32_tol(dtype), "dgamma")
+    check(host(dB).reshape(-1), rdb, f32_tol(dtype), "dbeta")
+    # models never share statistics: changing model 1's data leaves models 0 and 2 bit-identical
+    x2 = x.copy(); x2[1] = x2[1] * 2 + 1
+    Y2 = empty(x.shape, dtype)
+    hb.bn_fwd(B, Nb, C, 1, DT[dtype], dev(hi.snap(x2, dtype), dtype), s, G, Bt, 1e-5, 0.1, None, None, SM, SI, Y2, s,
+              hb.ACT_RELU, 0.0)
+    assert torch.equal(Y[0], Y2[0]) and torch.equal(Y[2], Y2[2]) and not torch.equal(Y[1], Y2[1])
+
+
+def test_bn_invariants_large_mean(hb):
+    # |mean| >> std: the shifted sums must keep fp32 accuracy; mean(y) = beta, var(y) = gamma^2 var/(var+eps)
+    B, Nb, C, L = 2, 4, 3, 1000
+    x = (hi.normal(35, (Nb, B * C, L)) * 0.01 + 100.0).astype(np.float32)
+    g, bt = np.full(B * C, 2.0, np.float32), np.full(B * C, 0.5, np.float32)
+    s = conv_strides(B, C, L)
+    SM, SI = empty((B * C,), torch.float32), empty((B * C,), torch.float32)
+    Y = empty(x.shape, "f32")
+    hb.bn_fwd(B, Nb, C, L, 0, dev(x), s, dev(g), dev(bt), 1e-5, 0.1, None, None, SM, SI, Y, s)
+    ry, rmean, rinv, _, _ = oa.bn_fwd(B, x, g, bt, 1e-5)
+    check(host(SM), rmean, 1e-6, "mean")
+    check(host(SI), rinv, 1e-4, "invstd")
+    y = host(Y)
+    assert np.abs(y.mean(axis=(0, 2)) - 0.5).max() < 1e-3
+
+
+# ------------------------------------------------------------------ point max-pool
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,C,L", [(2, 3, 50, 2500), (3, 2, 7, 250), (1, 1, 5, 3), (2, 2, 33, 64)])
+def test_maxpool_points(hb, dtype, B, Nb, C, L):
+    print(f"maxpool {dtype} B={B} Nb={Nb} C={C} L={L}", flush=True)
+    x = hi.normal(41, (Nb, B * C, L), dtype)
+    x = np.maximum(x, 0.0)                     # post-ReLU: many exact ties at zero
+    x[0, 0, :] = 0.0                           # all-equal row -> index 0
+    if L > 2:
+        x[0, 1, :] = -1.0; x[0, 1, 1] = 3.0; x[0, 1, L - 1] = 3.0   # first of equal maxima wins
+    X = dev(x, dtype)
+    xs = conv_strides(B, C, L)
+    # result lands directly in the linear layout [B][Nb][C]
+    vs = (Nb * C, C, 1)
+    V, I = empty((B, Nb, C), dtype), empty((B, Nb, C), torch.int32)
+    hb.maxpool_points(B, Nb, C, L, DT[dtype], X, xs, V, I, vs)
+    rv, ri = oa.maxpool_points_fwd(B, x)
+    rv = rv.reshape(Nb, B, C).transpose(1, 0, 2)
+    ri = ri.reshape(Nb, B, C).transpose(1, 0, 2)
+    assert np.array_equal(I.cpu().numpy(), ri)             # bit-exact indices
+    assert np.array_equal(host(V), rv)                     # values are copies
+    assert I[0, 0, 0].item() == 0
+    dv = hi.normal(42, (B, Nb, C), dtype)
+    dX = empty(x.shape, dtype)
+    hb.maxpool_points_bwd(B, Nb, C, L, DT[dtype], dev(dv, dtype), I, vs, dX, xs)
+    rdx = oa.maxpool_points_bwd(B, dv.transpose(1, 0, 2).reshape(Nb, B * C), ri.transpose(1, 0, 2).reshape(Nb, B * C), L)
+    assert np.array_equal(host(dX), rdx)
+
+
+# ------------------------------------------------------------------ Adam
+@pytest.mark.parametrize("gdtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,P", [(3, 4096 + 8), (2, 1023), (8, 100_000)])
+def test_adam(hb, gdtype, B, P):
+    hp = hi.adam_hparams(51, B)
+    th = hi.normal(52, (B, P)) * 0.1
+    m, v = np.zeros((B, P), np.float32), np.zeros((B, P), np.float32)
+    TH, M_, V_ = dev(th), dev(m), dev(v)
+    LP = empty((B, P), torch.bfloat16)
+    H = {k: dev(a) for k, a in hp.items()}
+    for dec in (0, 1):
+        th_r, m_r, v_r = th.copy(), m.copy(), v.copy()
+        TH.copy_(dev(th)); M_.zero_(); V_.zero_()
+        for t in range(1, 4):
+            g = hi.normal(60 + t, (B, P), gdtype)
+            hb.adam_step(B, P, DT[gdtype], TH, dev(g, gdtype), M_, V_, LP, H["lr"], H["beta1"], H["beta2"], H["eps"],
+                         H["wd"], t, dec)
+            th_r, m_r, v_r = oa.adam_step(B, th_r, g, m_r, v_r, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
+                                          hp["wd"], t, bool(dec))
+        check(host(TH), th_r, 1e-5, "theta")
+        check(host(M_), m_r, 1e-5, "m")
+        check(host(V_), v_r, 1e-5, "v")
+        assert torch.equal(LP, TH.to(torch.bfloat16))      # the low-precision copy is RNE of the new theta
+
+
+def test_adam_closed_form_and_routing(hb):
+    B, P = 3, 1000
+    th0 = hi.normal(53, (B, P))
+    g = hi.normal(54, (B, P))
+    lr = np.array([1e-2, 0.0, 1e-3], np.float32)
+    z = np.zeros(B, np.float32)
+    TH, M_, V_ = dev(th0), dev(np.zeros((B, P), np.float32)), dev(np.zeros((B, P), np.float32))
+    G = dev(g)
+    b1, b2, eps = dev(np.full(B, 0.8, np.float32)), dev(np.full(B, 0.95, np.float32)), dev(np.full(B, 1e-8, np.float32))
+    for t in range(1, 6):
+        hb.adam_step(B, P, 0, TH, G, M_, V_, None, dev(lr), b1, b2, eps, dev(z), t)
+    th = host(TH)
+    # constant gradient: theta_t = theta_0 - t lr g/(|g| + eps); lr = 0 leaves model 1 bit-unchanged
+    assert np.array_equal(th[1], th0[1].astype(np.float64))
+    for b in (0, 2):
+        ref = th0[b] - 5 * lr[b] * g[b] / (np.abs(g[b]) + 1e-8)
+        assert np.abs(th[b] - ref).max() < 2e-6
+
+
+# ------------------------------------------------------------------ support ops
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_activations_dropout(hb, dtype):
+    n = 10_007
+    x = hi.normal(71, (n,), dtype)
+    x[np.abs(x) < 1e-3] = 0.25
+    dy = hi.normal(72, (n,), dtype)
+    X, dY = dev(x, dtype), dev(dy, dtype)
+    Y, dX = empty((n,), dtype), empty((n,), dtype)
+    for act, oact in ((hb.ACT_RELU, oops.ACT_RELU), (hb.ACT_LEAKY, oops.ACT_LEAKY), (hb.ACT_TANH, oops.ACT_TANH),
+                      (hb.ACT_GELU, oops.ACT_GELU)):
+        hb.act_fwd(n, DT[dtype], X, Y, act, 0.2)
+        check(host(Y), oops.act_fwd(x, oact, 0.2), TOL[dtype], f"act{act}")
+        hb.act_bwd(n, DT[dtype], X, dY, dX, act, 0.2, 0)
+        check(host(dX), oops.act_bwd(x, dy, oact, 0.2), TOL[dtype], f"dact{act}")
+        if act != hb.ACT_GELU:
+            yst = host(Y)
+            hb.act_bwd(n, DT[dtype], Y, dY, dX, act, 0.2, 1)
+            ref = oops.act_bwd(x, dy, oact, 0.2) if act != hb.ACT_TANH else dy * (1 - yst * yst)
+            check(host(dX), ref, TOL[dtype], f"dact{act} from output")
+    mask = (np.random.default_rng(73).random(n) > 0.3).astype(np.uint8)
+    hb.dropout(n, DT[dtype], X, dev(mask), 0.3, Y)
+    check(host(Y), oops.dropout_fwd(x, mask, 0.3), TOL[dtype], "dropout")
+    # per-channel bias + activation in place on an [Nb][K][HW] tensor
+    Nb, K, HW = 3, 10, 37
+    t = hi.normal(74, (Nb, K, HW), dtype)
+    bias = hi.normal(75, (K,), dtype)
+    Tt = dev(t, dtype)
+    hb.bias_act_nchw(Nb, K, HW, DT[dtype], Tt, dev(bias, dtype), hb.ACT_TANH, 0.0)
+    check(host(Tt), np.tanh(t.astype(np.float64) + bias[None, :, None]), TOL[dtype], "bias_act")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,R,E", [(3, 200, 512), (2, 7, 100)])
+def test_layernorm(hb, dtype, B, R, E):
+    x = hi.snap(hi.normal(81, (B, R, E)) * 2 + 0.5, dtype)
+    w, b = hi.normal(82, (B, E)) * 0.5 + 1.0, hi.normal(83, (B, E)) * 0.2
+    dy = hi.normal(84, (B, R, E), dtype)
+    X, dY, Wt, Bt = dev(x, dtype), dev(dy, dtype), dev(w), dev(b)
+    SM, SI = empty((B, R), torch.float32), empty((B, R), torch.float32)
+    Y = empty(x.shape, dtype)
+    hb.layernorm_fwd(B, R, E, DT[dtype], X, Wt, Bt, 1e-5, SM, SI, Y)
+    ry, rmean, rinv = oa.layernorm_fwd(B, x, w, b, 1e-5)
+    check(host(Y), ry, TOL[dtype], "Y")
+    check(host(SM), rmean, 1e-5, "mean")
+    dX = empty(x.shape, dtype)
+    dw, db = empty((B, E), torch.float32), empty((B, E), torch.float32)
+    ws = torch.empty(hb.layernorm_bwd_workspace_bytes(B, R, E), dtype=torch.uint8, device="cuda")
+    hb.layernorm_bwd(B, R, E, DT[dtype], X, dY, Wt, SM, SI, dX, dw, db, ws)
+    rdx, rdw, rdb = oa.layernorm_bwd(B, x, dy, w, rmean, rinv)
+    check(host(dX), rdx, TOL[dtype], "dX")
+    check(host(dw), rdw, f32_tol(dtype), "dw")
+    check(host(db), rdb, f32_tol(dtype), "db")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_losses(hb, dtype):
+    B, R, K = 3, 77, 16
+    z = hi.normal(91, (B, R, K), dtype) * 2
+    lab = np.random.default_rng(92).integers(0, K, (B, R)).astype(np.int32)
+    loss, dz = empty((B,), torch.float32), empty((B, R, K), dtype)
+    hb.softmax_xent(B, R, K, DT[dtype], dev(z, dtype), dev(lab), loss, dz)
+    rl, rdz = oa.softmax_xent(B, z, lab)
+    check(host(loss), rl, 1e-5, "xent loss")
+    check(host(dz), rdz, TOL[dtype], "dlogits")
+    R2 = 5000
+    p, t = hi.normal(93, (B, R2), dtype), hi.normal(94, (B, R2), dtype)
+    dp = empty((B, R2), dtype)
+    hb.mse(B, R2, DT[dtype], dev(p, dtype), dev(t, dtype), loss, dp)
+    rl, rdp = oa.mse(B, p, t)
+    check(host(loss), rl, 1e-5, "mse loss")
+    check(host(dp), rdp, TOL[dtype], "dpred")
+    tb = (np.random.default_rng(95).random((B, R2)) > 0.5).astype(np.float32)
+    hb.bce_logits(B, R2, DT[dtype], dev(p, dtype), dev(tb, dtype), loss, dp)
+    rl, rdp = oa.bce_logits(B, p, tb)
+    check(host(loss), rl, 1e-5, "bce loss")
+    check(host(dp), rdp, TOL[dtype], "dlogits(bce)")
