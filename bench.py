@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused training array on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0] [--skip-serial] [--skip-cpu]
+
+A step is one forward + backward + Adam pass of the whole fused array over one
+synthetic batch that is already resident in HBM.  Prints ONE JSON line:
+fused samples/s summed over the B models (`value`), the same B models run one
+after another through the library with B = 1 (`serial_b1`), the roofline of the
+kernel that dominates the step (timed live with HIP events on the launch stream)
+and the CPU oracle timed on a bounded sample (`cpu_baseline`).
+"""
+from __future__ import annotations
+
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+from collections import defaultdict
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+# ------------------------------------------------------------------ tracing proxy
+class Tracer:
+    """Wraps the binding so that selected single-kernel entry points are bracketed
+    by HIP events on the stream they launch on (torch's current stream)."""
+
+    SINGLE_KERNEL = ("conv1x1_fwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
+                     "adam_step_multi", "linear_fwd")
+
+    def __init__(self, hb, torch):
+        self._hb, self._torch = hb, torch
+        self.events = []            # (label, bytes, start, end)
+        self.enabled = False
+
+    def __getattr__(self, name):
+        fn = getattr(self._hb, name)
+        if not callable(fn) or name not in self.SINGLE_KERNEL:
+            return fn
+
+        def wrapped(*a, **kw):
+            if not self.enabled:
+                return fn(*a, **kw)
+            s = self._torch.cuda.Event(enable_timing=True)
+            e = self._torch.cuda.Event(enable_timing=True)
+            s.record()
+            r = fn(*a, **kw)
+            e.record()
+            self.events.append((kernel_label(name, a), algorithmic_bytes(name, a), s, e))
+            return r
+        return wrapped
+
+    def summary(self):
+        self._torch.cuda.synchronize()
+        tot = defaultdict(lambda: [0, 0.0, 0.0])        # label -> [launches, ms, bytes]
+        for label, nbytes, s, e in self.events:
+            t = tot[label]
+            t[0] += 1
+            t[1] += s.elapsed_time(e)
+            t[2] += nbytes
+        return tot
+
+
+def _es(dtype):
+    return 2 if dtype == 1 else 4
+
+
+def kernel_label(name, a):
+    """Kernel symbol family an entry point launches (matches the rocprofv3 kernel names)."""
+    if name in ("bn_fwd", "bn_bwd"):
+        lay = "linear" if a[3] == 1 else "conv"
+        return f"{name}_{lay}_kernel"
+    if name in ("conv1x1_fwd", "linear_fwd"):
+        return "gemm_kernel(fwd)"
+    return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",
+            "adam_step_multi": "adam_multi_kernel"}[name]
+
+
+def algorithmic_bytes(name, a):
+    """Bytes that must cross HBM once: every operand in once, every result out once."""
+    if name == "bn_fwd":
+        B, Nb, C, L, dt = a[:5]
+        return 2 * B * Nb * C * L * _es(dt)
+    if name == "bn_bwd":
+        B, Nb, C, L, dt = a[:5]
+        return 3 * B * Nb * C * L * _es(dt)
+    if name == "conv1x1_fwd":
+        B, Nb, Ci, Co, L, dt = a[:6]
+        return (B * Nb * (Ci + Co) * L + B * Co * (Ci + 1)) * _es(dt)
+    if name == "linear_fwd":
+        B, M, Fx, Fy, dt = a[:5]
+        return B * (M * Fx + Fx * Fy + Fy + M * Fy) * _es(dt)
+    if name == "maxpool_points":
+        B, Nb, C, L, dt = a[:5]
+        return B * Nb * C * (L * _es(dt) + _es(dt) + 4)
+    if name == "maxpool_points_bwd":
+        B, Nb, C, L, dt = a[:5]
+        return B * Nb * C * (L * _es(dt) + _es(dt) + 4)
+    if name == "adam_step_multi":
+        B, off = a[0], a[1]
+        return B * off[-1] * (4 * 4 + 3 * 4 + (2 if a[7] is not None else 0))
+    return 0
+
+
+# ------------------------------------------------------------------ legs
+def time_steps(arr, torch, steps, warmup):
+    for _ in range(warmup):
+        arr.train_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        arr.train_step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(spec, budget_models=1, sample_nb=2):
+    """The oracle as it stands, on a bounded sample: `budget_models` model(s) and
+    `sample_nb` clouds of the full point count; cost is linear in B*Nb."""
+    import hfta_inputs as hi
+    from oracle import pointnet as opn
+    small = dataclasses.replace(spec, B=budget_models, Nb=sample_nb)
+    inp = hi.pointnet_cls_inputs(small)
+    states = [opn.init_state(inp["params"][b]) for b in range(small.B)]
+    t0 = time.perf_counter()
+    opn.array_train_step(small, states, inp, 1)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return dict(value=small.B * small.Nb / dt, unit="samples/s", cores=int(cores), kind="oracle",
+                sample=f"{small.B} model(s) x {small.Nb} clouds x {small.L} points, one fwd+bwd+Adam step "
+                       f"({dt:.1f} s), numpy float64; host has {os.cpu_count()} logical cores")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1"])
+    ap.add_argument("--skip-serial", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (models are independent and would shard over "
+              "the model index without any exchange); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import hfta_inputs as hi
+    from paper_2102_02344_amd import arrays, binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    spec = hi.spec_c1() if args.workload == "c1" else hi.spec_c0()
+    inp = hi.pointnet_cls_inputs(spec)
+
+    tracer = Tracer(binding, torch)
+    arrays.hb = tracer
+    arr = arrays.FusedPointNetCls(spec, inp)
+    # timed region: trace on, so the dominant kernel's launches are timed inside it
+    for _ in range(args.warmup):
+        arr.train_step()
+    torch.cuda.synchronize()
+    tracer.enabled = True
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        arr.train_step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    tracer.enabled = False
+    tot = tracer.summary()
+    samples = spec.B * spec.Nb
+    value = samples / sec
+
+    per_kernel = {k: dict(launches_per_step=v[0] // args.steps, ms_per_step=v[1] / args.steps,
+                          GBps=(v[2] / 1e9) / (v[1] / 1e3) if v[1] > 0 else None)
+                  for k, v in sorted(tot.items(), key=lambda kv: -kv[1][1])}
+    dom, dv = max(tot.items(), key=lambda kv: kv[1][1])
+    achieved = (dv[2] / dv[0]) / 1e9 / ((dv[1] / dv[0]) / 1e3)
+    roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBS, traffic=None,
+                    avg_launch_us=1e3 * dv[1] / dv[0], launches_per_step=dv[0] // args.steps,
+                    algorithmic_bytes_per_launch=dv[2] / dv[0],
+                    share_of_step=(dv[1] / args.steps) / (sec * 1e3))
+
+    serial = None
+    if not args.skip_serial:
+        arrays.hb = binding
+        per_model = []
+        models = []
+        for b in range(spec.B):
+            s1 = dataclasses.replace(spec, B=1)
+            i1 = dict(inp)
+            i1["points"] = np.ascontiguousarray(inp["points"][:, 3 * b:3 * b + 3])
+            i1["labels"] = inp["labels"][b:b + 1]
+            i1["params"] = inp["params"][b:b + 1]
+            i1["drop_mask"] = None if inp["drop_mask"] is None else inp["drop_mask"][b:b + 1]
+            for k in ("lr", "beta1", "beta2", "eps", "wd"):
+                i1[k] = inp[k][b:b + 1]
+            models.append(arrays.FusedPointNetCls(s1, i1))
+        nser = max(3, args.steps // 4)
+        for mdl in models:
+            per_model.append(time_steps(mdl, torch, nser, 2))
+        ssec = sum(per_model)          # B models, one after another
+        serial = dict(value=samples / ssec, unit="samples/s", ms_per_step_all_models=ssec * 1e3,
+                      fused_speedup=ssec / sec)
+        del models
+
+    cpu = None
+    if not args.skip_cpu:
+        cpu = cpu_baseline(spec)
+
+    out = {
+        "metric": "fused train samples/sec summed over B models",
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": spec.dtype, "data": "synthetic",
+        "config": {"workload": spec.name, "B": spec.B, "batch_per_model": spec.Nb, "points": spec.L,
+                   "conv": list(spec.conv), "fc": list(spec.fc), "step": "fwd+bwd+Adam"},
+        "roofline": roofline, "serial_b1": serial, "cpu_baseline": cpu, "kernels": per_kernel,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -203,6 +203,22 @@ int hfta_adam_step(int B, int64_t P, int grad_dtype,
                    const float* lr, const float* beta1, const float* beta2, const float* eps,
                    const float* weight_decay, int step_t, int decoupled_wd, void* stream);
 
+/* The same update over a parameter-major arena, still ONE launch.  The fused model
+ * keeps each fused parameter as its own tensor [B][n_j] (weights concatenated along
+ * the model dimension, as the fusion rules table lays them out), and the arena is
+ * those tensors back to back: fused parameter j occupies the flat element range
+ * [B*seg_offsets[j], B*seg_offsets[j+1]) as [B][n_j], n_j = seg_offsets[j+1]-seg_offsets[j].
+ *   seg_offsets: HOST array of nseg+1 per-model element offsets, seg_offsets[0] = 0,
+ *   strictly increasing; nseg <= HFTA_ADAM_MAX_SEGMENTS.  theta, grad, m, v,
+ *   theta_lowp: flat device buffers of B*seg_offsets[nseg] elements.
+ *   B <= HFTA_ADAM_MAX_MODELS.  Everything else as hfta_adam_step. */
+#define HFTA_ADAM_MAX_SEGMENTS 192
+#define HFTA_ADAM_MAX_MODELS 1024
+int hfta_adam_step_multi(int B, int nseg, const int64_t* seg_offsets, int grad_dtype,
+                         float* theta, const void* grad, float* m, float* v, void* theta_lowp,
+                         const float* lr, const float* beta1, const float* beta2, const float* eps,
+                         const float* weight_decay, int step_t, int decoupled_wd, void* stream);
+
 /* ------------------------------------------------------------------------
  * Support operators needed to close a training step (fusion rules table, rows
  * "ReLU", "LeakyReLU", "Tanh", "Dropout", "LayerNorm"; appendix "Fused Loss").

@@ -1,0 +1,271 @@
+"""Fused training arrays: B models of one architecture trained as one job.
+
+This module only sequences calls into the C ABI (``binding``) and owns the
+device buffers; every arithmetic step runs in the HIP kernels.  Parameters
+live in a parameter-major arena (each fused parameter is one ``[B][...]``
+tensor, as the fusion rules table concatenates weights along the model
+dimension), so one ``adam_step_multi`` launch updates all B models with their
+own learning rate, betas and weight decay.
+
+Layouts: point-wise activations ``[Nb, B*C, L]`` (the table's Conv1d /
+BatchNorm1d layout), head activations ``[B, Nb, F]`` (the table's baddbmm
+layout); the max-pool writes straight from the first into the second.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Tuple
+
+import numpy as np
+import torch
+
+from . import binding as hb
+
+_TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+_DT = {"f32": hb.F32, "bf16": hb.BF16}
+
+
+def _cs(B, C, L):
+    return (C * L, B * C * L, L, 1)
+
+
+class FusedPointNetCls:
+    """PointNet-classification-style array (per-point k=1 convolutions + BatchNorm +
+    ReLU, max over points, fully connected head, softmax cross-entropy, Adam)."""
+
+    BN_EPS = 1e-5
+    BN_MOMENTUM = 0.1
+
+    def __init__(self, spec, inp: dict, device: str = "cuda"):
+        self.spec = spec
+        self.B, self.Nb, self.L = spec.B, spec.Nb, spec.L
+        self.dtype = spec.dtype
+        self.dt = _DT[spec.dtype]
+        self.tdt = _TDT[spec.dtype]
+        self.dev = torch.device(device)
+        B, Nb, L = self.B, self.Nb, self.L
+
+        # ---- parameter arena (parameter-major) --------------------------------
+        import hfta_inputs as hi
+        self.shapes: List[Tuple[str, Tuple[int, ...]]] = hi.pointnet_cls_param_shapes(spec)
+        off = [0]
+        for _, shp in self.shapes:
+            off.append(off[-1] + int(np.prod(shp)))
+        self.seg_offsets = off
+        P = off[-1]
+        self.P = P
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.theta = torch.empty(B * P, **f32)
+        self.grad = torch.zeros(B * P, **f32)
+        self.m = torch.zeros(B * P, **f32)
+        self.v = torch.zeros(B * P, **f32)
+        self.lowp = torch.empty(B * P, dtype=torch.bfloat16, device=self.dev) if spec.dtype == "bf16" else None
+        host = np.empty(B * P, np.float32)
+        for j, (name, shp) in enumerate(self.shapes):
+            n = off[j + 1] - off[j]
+            blk = np.stack([inp["params"][b][name].reshape(-1) for b in range(B)])
+            host[B * off[j]:B * off[j] + B * n] = blk.reshape(-1)
+        self.theta.copy_(torch.from_numpy(host))
+        if self.lowp is not None:
+            self.lowp.copy_(self.theta)           # initial cast only; afterwards Adam writes it
+        self.hp = {k: torch.from_numpy(np.asarray(inp[k], np.float32)).to(self.dev)
+                   for k in ("lr", "beta1", "beta2", "eps", "wd")}
+        self.t = 0
+
+        # ---- BatchNorm running statistics / saved statistics -------------------
+        self.running: Dict[str, torch.Tensor] = {}
+        self.saved: Dict[str, torch.Tensor] = {}
+        for name, shp in self.shapes:
+            if name.endswith(".bn.g"):
+                k = name[:-2]
+                self.running[k + ".rm"] = torch.zeros(B * shp[0], **f32)
+                self.running[k + ".rv"] = torch.ones(B * shp[0], **f32)
+                self.saved[k + ".mean"] = torch.empty(B * shp[0], **f32)
+                self.saved[k + ".invstd"] = torch.empty(B * shp[0], **f32)
+
+        # ---- activations ----------------------------------------------------------
+        act = dict(dtype=self.tdt, device=self.dev)
+        self.nconv = len(spec.conv) - 1
+        self.nfc = len(spec.fc) - 1
+        self.z = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:]]
+        self.a = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:]]
+        cmax = max(spec.conv[1:])
+        self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
+        Cp = spec.conv[-1]
+        self.pooled = torch.empty(B, Nb, Cp, **act)
+        self.pool_idx = torch.empty(B, Nb, Cp, dtype=torch.int32, device=self.dev)
+        self.fz = [torch.empty(B, Nb, f, **act) for f in spec.fc[1:]]
+        self.fh = [torch.empty(B, Nb, f, **act) for f in spec.fc[1:-1]]
+        self.fdrop = torch.empty(B, Nb, spec.fc[-2], **act) if spec.dropout_p > 0 else None
+        fmax = max(spec.fc)
+        self.fd = [torch.empty(B * Nb * fmax, **act) for _ in range(2)]
+        self.loss = torch.empty(B, **f32)
+        ws = 4
+        for i in range(self.nconv):
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
+        for i in range(self.nfc):
+            ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+
+        # ---- inputs -----------------------------------------------------------------
+        self.points = torch.from_numpy(inp["points"]).to(self.tdt).to(self.dev)
+        self.labels = torch.from_numpy(inp["labels"]).to(self.dev)
+        self.drop_mask = None
+        if spec.dropout_p > 0:
+            self.drop_mask = torch.from_numpy(inp["drop_mask"]).to(self.dev)
+
+    # ------------------------------------------------------------------ views
+    def _seg(self, buf: torch.Tensor, name: str) -> torch.Tensor:
+        j = [n for n, _ in self.shapes].index(name)
+        o, n = self.seg_offsets[j], self.seg_offsets[j + 1] - self.seg_offsets[j]
+        return buf[self.B * o:self.B * (o + n)]
+
+    def w(self, name: str) -> torch.Tensor:
+        """Weights as the GEMMs read them (storage dtype)."""
+        return self._seg(self.lowp if self.lowp is not None else self.theta, name)
+
+    def master(self, name: str) -> torch.Tensor:
+        return self._seg(self.theta, name)
+
+    def g(self, name: str) -> torch.Tensor:
+        return self._seg(self.grad, name)
+
+    def param_host(self, buf: torch.Tensor, name: str, b: int) -> np.ndarray:
+        shp = dict(self.shapes)[name]
+        return self._seg(buf, name).view(self.B, *shp)[b].float().cpu().numpy()
+
+    # ------------------------------------------------------------------ one step
+    def forward_backward(self, probe=None):
+        """One forward + backward pass.  ``probe(op, **tensors)``, if given, is called after
+        every library call with the tensors that call read and wrote (tests use it to check
+        each operator in place against the oracle on the very bits the GPU consumed)."""
+        s, B, Nb, L, dt = self.spec, self.B, self.Nb, self.L, self.dt
+        eps, mom = self.BN_EPS, self.BN_MOMENTUM
+        P = probe if probe is not None else (lambda op, **kw: None)
+        # per-point MLP
+        x, ci = self.points, s.conv[0]
+        for i in range(self.nconv):
+            co = s.conv[i + 1]
+            k = f"conv{i}"
+            hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
+                           self.z[i], _cs(B, co, L))
+            P("conv1x1_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
+            hb.bn_fwd(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), self.master(k + ".bn.g"), self.master(k + ".bn.b"),
+                      eps, mom, self.running[k + ".bn.rm"], self.running[k + ".bn.rv"],
+                      self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], self.a[i], _cs(B, co, L), hb.ACT_RELU)
+            P("bn_fwd", layer=k, layout="conv", x=self.z[i], g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"),
+              y=self.a[i], mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"])
+            x, ci = self.a[i], co
+        Cp = ci
+        vs = (Nb * Cp, Cp, 1)
+        hb.maxpool_points(B, Nb, Cp, L, dt, x, _cs(B, Cp, L), self.pooled, self.pool_idx, vs)
+        P("maxpool_points", x=x, v=self.pooled, idx=self.pool_idx)
+        # head
+        h, fx = self.pooled, s.fc[0]
+        for i in range(self.nfc):
+            fy = s.fc[i + 1]
+            k = f"fc{i}"
+            last = i == self.nfc - 1
+            if last or s.fc_bn:
+                hb.linear_fwd(B, Nb, fx, fy, dt, h, self.w(k + ".w"), self.w(k + ".b"), self.fz[i])
+                P("linear_fwd", layer=k, x=h, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.fz[i], act=0)
+                if not last:
+                    ls = (Nb * fy, fy, 1, 1)
+                    hb.bn_fwd(B, Nb, fy, 1, dt, self.fz[i], ls, self.master(k + ".bn.g"), self.master(k + ".bn.b"),
+                              eps, mom, self.running[k + ".bn.rm"], self.running[k + ".bn.rv"],
+                              self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], self.fh[i], ls, hb.ACT_RELU)
+                    P("bn_fwd", layer=k, layout="linear", x=self.fz[i], g=self.master(k + ".bn.g"),
+                      b=self.master(k + ".bn.b"), y=self.fh[i], mean=self.saved[k + ".bn.mean"],
+                      invstd=self.saved[k + ".bn.invstd"])
+            else:
+                hb.linear_fwd(B, Nb, fx, fy, dt, h, self.w(k + ".w"), self.w(k + ".b"), self.fh[i], hb.ACT_RELU)
+                P("linear_fwd", layer=k, x=h, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.fh[i], act=1)
+            if last:
+                h = self.fz[i]
+            else:
+                h = self.fh[i]
+                if i == self.nfc - 2 and s.dropout_p > 0:
+                    hb.dropout(B * Nb * fy, dt, h, self.drop_mask, s.dropout_p, self.fdrop)
+                    P("dropout", x=h, mask=self.drop_mask, y=self.fdrop)
+                    h = self.fdrop
+            fx = fy
+        logits = h
+        K = s.fc[-1]
+        d = self.fd[0][:B * Nb * K]
+        hb.softmax_xent(B, Nb, K, dt, logits, self.labels, self.loss, d)
+        P("softmax_xent", logits=logits, labels=self.labels, loss=self.loss, d=d.view(B, Nb, K))
+
+        # backward: head
+        cur = 0
+        for i in reversed(range(self.nfc)):
+            fx, fy = s.fc[i], s.fc[i + 1]
+            k = f"fc{i}"
+            last = i == self.nfc - 1
+            if not last:
+                n = B * Nb * fy
+                if i == self.nfc - 2 and s.dropout_p > 0:
+                    nd = self.fd[cur ^ 1][:n]
+                    hb.dropout(n, dt, d, self.drop_mask, s.dropout_p, nd)
+                    P("dropout", x=d.view(B, Nb, fy), mask=self.drop_mask, y=nd.view(B, Nb, fy))
+                    d, cur = nd, cur ^ 1
+                nd = self.fd[cur ^ 1][:n]
+                if s.fc_bn:
+                    ls = (Nb * fy, fy, 1, 1)
+                    hb.bn_bwd(B, Nb, fy, 1, dt, self.fz[i], ls, d, ls, self.master(k + ".bn.g"),
+                              self.master(k + ".bn.b"), self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
+                              nd, ls, self.g(k + ".bn.g"), self.g(k + ".bn.b"), hb.ACT_RELU)
+                    P("bn_bwd", layer=k, layout="linear", x=self.fz[i], dy=d.view(B, Nb, fy),
+                      g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"],
+                      invstd=self.saved[k + ".bn.invstd"], dx=nd.view(B, Nb, fy), dg=self.g(k + ".bn.g"),
+                      db=self.g(k + ".bn.b"))
+                else:
+                    hb.act_bwd(n, dt, self.fh[i], d, nd, hb.ACT_RELU, 0.0, 1)
+                    P("relu_bwd_from_output", y=self.fh[i], dy=d.view(B, Nb, fy), dx=nd.view(B, Nb, fy))
+                d, cur = nd, cur ^ 1
+            if i == 0:
+                hin = self.pooled
+            elif i == self.nfc - 1 and s.dropout_p > 0:
+                hin = self.fdrop
+            else:
+                hin = self.fh[i - 1]
+            nd = self.fd[cur ^ 1][:B * Nb * fx]
+            hb.linear_bwd(B, Nb, fx, fy, dt, hin, self.w(k + ".w"), d, nd, self.g(k + ".w"), self.g(k + ".b"), self.ws)
+            P("linear_bwd", layer=k, x=hin, w=self.w(k + ".w"), dy=d.view(B, Nb, fy), dx=nd.view(B, Nb, fx),
+              dw=self.g(k + ".w"), db=self.g(k + ".b"))
+            d, cur = nd, cur ^ 1
+
+        # backward: pool and per-point MLP
+        Cp = s.conv[-1]
+        n = Nb * B * Cp * L
+        da = self.dbuf[0][:n]
+        hb.maxpool_points_bwd(B, Nb, Cp, L, dt, d, self.pool_idx, (Nb * Cp, Cp, 1), da, _cs(B, Cp, L))
+        P("maxpool_points_bwd", dv=d.view(B, Nb, Cp), idx=self.pool_idx, dx=da.view(Nb, B * Cp, L))
+        cur = 0
+        for i in reversed(range(self.nconv)):
+            ci, co = s.conv[i], s.conv[i + 1]
+            k = f"conv{i}"
+            cs = _cs(B, co, L)
+            dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
+            hb.bn_bwd(B, Nb, co, L, dt, self.z[i], cs, da, cs, self.master(k + ".bn.g"), self.master(k + ".bn.b"),
+                      self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], dz, cs, self.g(k + ".bn.g"),
+                      self.g(k + ".bn.b"), hb.ACT_RELU)
+            P("bn_bwd", layer=k, layout="conv", x=self.z[i], dy=da.view(Nb, B * co, L), g=self.master(k + ".bn.g"),
+              b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
+              dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"), db=self.g(k + ".bn.b"))
+            xin = self.points if i == 0 else self.a[i - 1]
+            dxin = None if i == 0 else self.dbuf[cur][:Nb * B * ci * L]
+            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), dz, cs,
+                           dxin, None if i == 0 else _cs(B, ci, L), self.g(k + ".w"), self.g(k + ".b"), self.ws)
+            P("conv1x1_bwd", layer=k, x=xin, w=self.w(k + ".w"), dy=dz.view(Nb, B * co, L),
+              dx=None if i == 0 else dxin.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"))
+            da = dxin
+        return self.loss
+
+    def adam(self):
+        self.t += 1
+        hb.adam_step_multi(self.B, self.seg_offsets, hb.F32, self.theta, self.grad, self.m, self.v, self.lowp,
+                           self.hp["lr"], self.hp["beta1"], self.hp["beta2"], self.hp["eps"], self.hp["wd"], self.t)
+
+    def train_step(self):
+        loss = self.forward_backward()
+        self.adam()
+        return loss

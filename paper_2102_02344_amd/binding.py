@@ -55,6 +55,7 @@ _SIGS = {
     "hfta_maxpool_points": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p]),
     "hfta_maxpool_points_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _s4, _p, _s4, _p]),
     "hfta_adam_step": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
+    "hfta_adam_step_multi": (_i, [_i, _i, _s4, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
     "hfta_act_fwd": (_i, [_i64, _i, _p, _p, _i, _f, _p]),
     "hfta_act_bwd": (_i, [_i64, _i, _p, _p, _p, _i, _f, _i, _p]),
     "hfta_bias_act_nchw": (_i, [_i64, _i64, _i64, _i, _p, _p, _i, _f, _p]),
@@ -197,6 +198,15 @@ def adam_step(B, P, grad_dtype, theta, grad, m, v, theta_lowp, lr, beta1, beta2,
     _check(_lib.hfta_adam_step(B, P, grad_dtype, _ptr(theta), _ptr(grad), _ptr(m), _ptr(v), _ptr(theta_lowp),
                                _ptr(lr), _ptr(beta1), _ptr(beta2), _ptr(eps), _ptr(weight_decay), step_t,
                                decoupled_wd, _stream(stream)), "hfta_adam_step")
+
+
+def adam_step_multi(B, seg_offsets, grad_dtype, theta, grad, m, v, theta_lowp, lr, beta1, beta2, eps,
+                    weight_decay, step_t, decoupled_wd=0, stream=None):
+    nseg = len(seg_offsets) - 1
+    _check(_lib.hfta_adam_step_multi(B, nseg, _strides(seg_offsets, nseg + 1), grad_dtype, _ptr(theta), _ptr(grad),
+                                     _ptr(m), _ptr(v), _ptr(theta_lowp), _ptr(lr), _ptr(beta1), _ptr(beta2),
+                                     _ptr(eps), _ptr(weight_decay), step_t, decoupled_wd, _stream(stream)),
+           "hfta_adam_step_multi")
 
 
 def act_fwd(count, dtype, X, Y, act, slope=0.0, stream=None):

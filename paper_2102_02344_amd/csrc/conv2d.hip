@@ -1,10 +1,425 @@
-// Fused Conv2d with groups = B (placeholder until the implicit-GEMM kernel lands).
-#include "common.h"
+// Fused Conv2d with groups = B as an implicit GEMM on the matrix cores.
+//
+// The B models' convolutions are one launch: the model index is a batch
+// dimension of the GEMM, never a channel-mixing dimension (fusion rules table,
+// row "Conv2d": grouped convolution with G = B).  No im2col buffer exists: the
+// operand tiles are gathered from the image / gradient tensors while they are
+// staged into LDS, then the same 128x128 MFMA tile loop as the batched GEMM core
+// runs on them.
+//
+//   forward        per (b, n):  Y[o][pix]  = sum_k W[o][k]   * col(X)[k][pix],   k = (c, ky, kx)
+//   data gradient  per (b, n):  dX[c][ipx] = sum_k Wt[c][k]  * colT(dY)[k][ipx], k = (o, ky, kx)
+//   weight grad    per b:       dW[o][j]   = sum_{n,pix} dY[o][pix] * col(X)[pix][j], j = (c, ky, kx)
+//
+// The weight gradient's reduction over (n, pix) is split across workgroups with
+// fp32 partials summed in a fixed order.
+#include "gemm.h"
+
 using namespace hfta;
-extern "C" {
-int hfta_conv2d_grouped_fwd(int, int, int, int, int, int, int, int, int, int, int, const void*, const void*, const void*,
-                            void*, int, float, void*) { return HFTA_EUNSUPPORTED; }
-size_t hfta_conv2d_grouped_bwd_workspace_bytes(int, int, int, int, int, int, int, int, int, int, int) { return 0; }
-int hfta_conv2d_grouped_bwd(int, int, int, int, int, int, int, int, int, int, int, const void*, const void*, const void*,
-                            void*, float*, float*, void*, size_t, void*) { return HFTA_EUNSUPPORTED; }
+
+namespace {
+
+struct FastDiv {
+  int d, shift;  // shift >= 0 when d is a power of two
+  __host__ static FastDiv make(int d) {
+    FastDiv f{d, -1};
+    if (d > 0 && (d & (d - 1)) == 0) { f.shift = 0; while ((1 << f.shift) < d) ++f.shift; }
+    return f;
+  }
+  __device__ __forceinline__ int div(int x) const { return shift >= 0 ? (x >> shift) : (x / d); }
+  __device__ __forceinline__ void divmod(int x, int& q, int& r) const { q = div(x); r = x - q * d; }
+};
+
+enum { CONV_FWD = 0, CONV_DX = 1, CONV_DW = 2 };
+
+struct ConvArgs {
+  const void* X;    // fwd/dW: input image; dX: unused
+  const void* Wt;   // fwd/dX: weights
+  const void* dY;   // dX/dW: output gradient
+  void* Out;        // fwd: Y; dX: dX; dW: dW (fp32) or unused when splits > 1
+  const void* bias;
+  float* partial;
+  int B, Nb, Ci, Co, H, W, Ho, Wo, kh, kw, stride, pad;
+  int M, N, K, S;   // GEMM view; S = outer reduction segments (dW: Nb)
+  int tiles_n, tiles_per_seg, total_tiles, splits;
+  int act, a_vec;
+  float slope;
+  FastDiv d_kw, d_khkw, d_wo, d_w;
+};
+
+// ---- gather helpers ---------------------------------------------------------
+// forward / weight-gradient im2col element: X[n][b*Ci + c][s*y + ky - p][s*x + kx - p] or 0
+template <typename T>
+__device__ __forceinline__ T x_at(const ConvArgs& p, const T* xb /* X + (n*B*Ci + b*Ci)*H*W */, int c, int iy, int ix) {
+  if ((unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W) return xb[((int64_t)c * p.H + iy) * p.W + ix];
+  return T(0);
 }
+// data-gradient element: dY[n][b*Co + o][(iy + p - ky)/s][(ix + p - kx)/s] when both divisions are exact
+template <typename T>
+__device__ __forceinline__ T dy_at(const ConvArgs& p, const T* dyb, int o, int ty, int tx) {
+  if (ty < 0 || tx < 0) return T(0);
+  int y = ty, x = tx;
+  if (p.stride != 1) {
+    y = ty / p.stride; x = tx / p.stride;
+    if (y * p.stride != ty || x * p.stride != tx) return T(0);
+  }
+  if (y < p.Ho && x < p.Wo) return dyb[((int64_t)o * p.Ho + y) * p.Wo + x];
+  return T(0);
+}
+
+// Stages one 128 x BK operand tile whose rows are GEMM rows/columns and whose 16-byte groups run
+// along k, in the same LDS layout the MFMA loop of the GEMM core reads.
+template <typename T, int MODE>
+__global__ __launch_bounds__(GEMM_THREADS) void conv_gemm_kernel(ConvArgs p) {
+  constexpr int BK = GemmT<T>::BK, KG = GemmT<T>::KG, NV = GemmT<T>::NV, KQ = GemmT<T>::KQ;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][GEMM_TILE_BYTES];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  const int m0 = tile_m * GEMM_BM, n0 = tile_n * GEMM_BN;
+  const int split = blockIdx.z % p.splits, g = blockIdx.z / p.splits;
+  // fwd / dX: g = b * Nb + n ; dW: g = b
+  const int b = MODE == CONV_DW ? g : g / p.Nb;
+  const int nimg = MODE == CONV_DW ? 0 : g % p.Nb;
+  const int64_t HW = (int64_t)p.H * p.W, HoWo = (int64_t)p.Ho * p.Wo;
+  const int khkw = p.kh * p.kw;
+
+  const T* X = reinterpret_cast<const T*>(p.X);
+  const T* Wt = reinterpret_cast<const T*>(p.Wt);
+  const T* dY = reinterpret_cast<const T*>(p.dY);
+
+  const int t_begin = (int)((int64_t)p.total_tiles * split / p.splits);
+  const int t_end = (int)((int64_t)p.total_tiles * (split + 1) / p.splits);
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // thread -> elements.  A side (k-contiguous groups): group ga of rows ra and ra + 64.
+  const int ga = t & 3, ra = t >> 2;
+  // B side: k-quad kq, n-group ng (NV consecutive GEMM columns)
+  const int kq = t % KQ, ng = t / KQ;
+  // loop-invariant decomposition of this thread's B columns
+  int cn_a[NV], cn_b[NV], cn_c[NV];   // fwd: (y, x, -) ; dX: (iy, ix, -) ; dW: (c, ky, kx)
+#pragma unroll
+  for (int e = 0; e < NV; ++e) {
+    const int n = n0 + ng * NV + e;
+    if (MODE == CONV_FWD) { p.d_wo.divmod(n, cn_a[e], cn_b[e]); cn_c[e] = 0; }
+    else if (MODE == CONV_DX) { p.d_w.divmod(n, cn_a[e], cn_b[e]); cn_c[e] = 0; }
+    else { int r; p.d_khkw.divmod(n, cn_a[e], r); p.d_kw.divmod(r, cn_b[e], cn_c[e]); }
+  }
+
+  uint4 qa[2];
+  uint2 qb[4];
+  auto issue = [&](int tt) {
+    const int seg = tt / p.tiles_per_seg;
+    const int k0 = (tt - seg * p.tiles_per_seg) * BK;
+    // ---------------- A operand
+    {
+      const int k = k0 + ga * KG;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int m = m0 + ra + 64 * h;
+        T tmp[KG];
+        if (MODE == CONV_FWD) {
+          // W[b*Co + m][k], k-contiguous
+          const T* src = Wt + ((int64_t)b * p.Co + m) * p.K + k;
+          if (p.a_vec && m < p.M && k + KG <= p.K && (p.K % KG) == 0) {
+            qa[h] = *reinterpret_cast<const uint4*>(src);
+            continue;
+          }
+#pragma unroll
+          for (int e = 0; e < KG; ++e) tmp[e] = (m < p.M && k + e < p.K) ? src[e] : T(0);
+        } else if (MODE == CONV_DX) {
+          // Wt[c = m][k = (o, tap)] = W[b*Co + o][c][tap]: runs of kh*kw taps are contiguous
+          if (p.a_vec && m < p.M && k + KG <= p.K && (khkw % KG) == 0) {
+            const int o = p.d_khkw.div(k), tap = k - o * khkw;
+            qa[h] = *reinterpret_cast<const uint4*>(Wt + (((int64_t)b * p.Co + o) * p.Ci + m) * khkw + tap);
+            continue;
+          }
+#pragma unroll
+          for (int e = 0; e < KG; ++e) {
+            const int kk = k + e;
+            if (m < p.M && kk < p.K) {
+              const int o = p.d_khkw.div(kk), tap = kk - o * khkw;
+              tmp[e] = Wt[(((int64_t)b * p.Co + o) * p.Ci + m) * khkw + tap];
+            } else tmp[e] = T(0);
+          }
+        } else {
+          // dY[seg][b*Co + m][pix = k], k-contiguous
+          const T* src = dY + (((int64_t)seg * p.B + b) * p.Co + m) * HoWo + k;
+          if (p.a_vec && m < p.M && k + KG <= p.K && (HoWo % KG) == 0) {
+            qa[h] = *reinterpret_cast<const uint4*>(src);
+            continue;
+          }
+#pragma unroll
+          for (int e = 0; e < KG; ++e) tmp[e] = (m < p.M && k + e < p.K) ? src[e] : T(0);
+        }
+        qa[h] = *reinterpret_cast<const uint4*>(tmp);
+      }
+    }
+    // ---------------- B operand: 4 k x NV n gathered elements
+    {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = k0 + 4 * kq + j;
+        T tmp[NV];
+        if (MODE == CONV_FWD) {
+          const T* xb = X + ((int64_t)nimg * p.B + b) * p.Ci * HW;
+          int c, r, ky, kx;
+          p.d_khkw.divmod(k, c, r);
+          p.d_kw.divmod(r, ky, kx);
+#pragma unroll
+          for (int e = 0; e < NV; ++e) {
+            const int n = n0 + ng * NV + e;
+            tmp[e] = (k < p.K && n < p.N) ? x_at<T>(p, xb, c, cn_a[e] * p.stride + ky - p.pad, cn_b[e] * p.stride + kx - p.pad) : T(0);
+          }
+        } else if (MODE == CONV_DX) {
+          const T* dyb = dY + ((int64_t)nimg * p.B + b) * p.Co * HoWo;
+          int o, r, ky, kx;
+          p.d_khkw.divmod(k, o, r);
+          p.d_kw.divmod(r, ky, kx);
+#pragma unroll
+          for (int e = 0; e < NV; ++e) {
+            const int n = n0 + ng * NV + e;
+            tmp[e] = (k < p.K && n < p.N) ? dy_at<T>(p, dyb, o, cn_a[e] + p.pad - ky, cn_b[e] + p.pad - kx) : T(0);
+          }
+        } else {
+          const T* xb = X + ((int64_t)seg * p.B + b) * p.Ci * HW;
+          int y, x;
+          p.d_wo.divmod(k, y, x);
+#pragma unroll
+          for (int e = 0; e < NV; ++e) {
+            const int n = n0 + ng * NV + e;
+            tmp[e] = (k < p.K && n < p.N) ? x_at<T>(p, xb, cn_a[e], y * p.stride + cn_b[e] - p.pad, x * p.stride + cn_c[e] - p.pad) : T(0);
+          }
+        }
+        qb[j] = *reinterpret_cast<const uint2*>(tmp);
+      }
+    }
+  };
+  auto stash = [&](int buf) {
+    store_kc(smem[buf][0], qa, t);
+    if (sizeof(T) == 2) store_nc_bf16(smem[buf][1], qb, t);
+    else store_nc_f32(smem[buf][1], qb, t);
+  };
+
+  if (t_begin < t_end) {
+    issue(t_begin);
+    stash(0);
+    __syncthreads();
+    int buf = 0;
+    for (int tt = t_begin; tt < t_end; ++tt) {
+      const bool more = tt + 1 < t_end;
+      if (more) issue(tt + 1);
+      mma_tile<T>(acc, smem[buf][0], smem[buf][1], wm, wn, lane);
+      if (more) stash(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+
+  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  if (MODE == CONV_DW) {
+    // fp32 output [b][M][N] (contiguous), through the partial buffer when split
+    float* base = p.splits > 1 ? p.partial + ((int64_t)split * p.B + b) * (int64_t)p.M * p.N
+                               : reinterpret_cast<float*>(p.Out) + (int64_t)b * p.M * p.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn * 64 + j * 32 + col_l;
+        if (n >= p.N) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+          if (m < p.M) base[(int64_t)m * p.N + n] = acc[i][j][v];
+        }
+      }
+    return;
+  }
+  // fwd: Y[n][b*Co + m][pix]; dX: dX[n][b*Ci + m][ipx]
+  T* out = reinterpret_cast<T*>(p.Out) + (((int64_t)nimg * p.B + b) * p.M) * (int64_t)p.N;
+  const T* bias = (MODE == CONV_FWD && p.bias) ? reinterpret_cast<const T*>(p.bias) + (int64_t)b * p.Co : nullptr;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn * 64 + j * 32 + col_l;
+      if (n >= p.N) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+        if (m >= p.M) continue;
+        float x = acc[i][j][v];
+        if (bias) x += Elem<T>::load(bias + m);
+        if (MODE == CONV_FWD) x = apply_act(x, p.act, p.slope);
+        Elem<T>::store(out + (int64_t)m * p.N + n, x);
+      }
+    }
+}
+
+__global__ void conv_splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t count, int splits) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  float s = 0.f;
+  for (int k = 0; k < splits; ++k) s += partial[(int64_t)k * count + i];
+  out[i] = s;
+}
+
+// dbias[b*Co + o] = sum over (n, pix) of dY[n][b*Co + o][pix]
+template <typename T>
+__global__ __launch_bounds__(256) void conv_dbias_kernel(const T* __restrict__ dY, float* __restrict__ out, int Nb, int K, int64_t HoWo) {
+  __shared__ float part[4];
+  const int k = blockIdx.x;
+  float s = 0.f;
+  const int64_t total = (int64_t)Nb * HoWo;
+  for (int64_t i = threadIdx.x; i < total; i += 256) {
+    const int64_t n = i / HoWo, r = i - n * HoWo;
+    s += Elem<T>::load(dY + (n * K + k) * HoWo + r);
+  }
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) out[k] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+struct ConvGeom { int Ho, Wo; };
+
+int check_conv(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype, ConvGeom* g) {
+  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 ||
+      !valid_dtype(dtype))
+    return HFTA_EINVAL;
+  if (H + 2 * pad < kh || W + 2 * pad < kw) return HFTA_EINVAL;
+  g->Ho = (H + 2 * pad - kh) / stride + 1;
+  g->Wo = (W + 2 * pad - kw) / stride + 1;
+  const int64_t lim = 0x7fffffffLL;
+  if ((int64_t)Ci * kh * kw > lim || (int64_t)Ci * H * W > lim || (int64_t)Co * g->Ho * g->Wo > lim ||
+      (int64_t)Co * kh * kw > lim || (int64_t)Nb * g->Ho * g->Wo > lim)
+    return HFTA_EINVAL;
+  if ((int64_t)B * Nb > 65535) return HFTA_EUNSUPPORTED;
+  return HFTA_OK;
+}
+
+ConvArgs base_args(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, ConvGeom g) {
+  ConvArgs a{};
+  a.B = B; a.Nb = Nb; a.Ci = Ci; a.Co = Co; a.H = H; a.W = W; a.Ho = g.Ho; a.Wo = g.Wo;
+  a.kh = kh; a.kw = kw; a.stride = stride; a.pad = pad;
+  a.S = 1; a.splits = 1; a.act = HFTA_ACT_NONE; a.slope = 0.f;
+  a.d_kw = FastDiv::make(kw); a.d_khkw = FastDiv::make(kh * kw); a.d_wo = FastDiv::make(g.Wo); a.d_w = FastDiv::make(W);
+  return a;
+}
+
+void finish_tiles(ConvArgs& a, int dtype) {
+  const int BK = dtype == HFTA_BF16 ? GemmT<bf16_raw>::BK : GemmT<float>::BK;
+  a.tiles_n = (a.N + GEMM_BN - 1) / GEMM_BN;
+  a.tiles_per_seg = (a.K + BK - 1) / BK;
+  a.total_tiles = a.S * a.tiles_per_seg;
+}
+
+int dw_splits(const ConvArgs& a) {
+  const int64_t tiles = (int64_t)((a.M + GEMM_BM - 1) / GEMM_BM) * a.tiles_n * a.B;
+  if (tiles >= 512 || a.total_tiles < 16) return 1;
+  int64_t want = (1024 + tiles - 1) / tiles, cap = a.total_tiles / 8;
+  if (want > cap) want = cap;
+  if (want > 256) want = 256;
+  if ((int64_t)a.B * want > 65535) want = 65535 / a.B;
+  return want < 1 ? 1 : (int)want;
+}
+
+template <int MODE>
+int launch_conv(const ConvArgs& a, int dtype, unsigned gz, hipStream_t st) {
+  dim3 grid((unsigned)(((a.M + GEMM_BM - 1) / GEMM_BM) * a.tiles_n), 1, gz);
+  if (dtype == HFTA_BF16) hipLaunchKernelGGL((conv_gemm_kernel<bf16_raw, MODE>), grid, dim3(GEMM_THREADS), 0, st, a);
+  else hipLaunchKernelGGL((conv_gemm_kernel<float, MODE>), grid, dim3(GEMM_THREADS), 0, st, a);
+  return launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype,
+                            const void* X, const void* Wt, const void* bias, void* Y, int act, float act_slope,
+                            void* stream) {
+  ConvGeom g;
+  int rc = check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g);
+  if (rc != HFTA_OK) return rc;
+  if (!X || !Wt || !Y || !valid_act(act)) return HFTA_EINVAL;
+  ConvArgs a = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
+  a.X = X; a.Wt = Wt; a.Out = Y; a.bias = bias; a.act = act; a.slope = act_slope;
+  a.a_vec = reinterpret_cast<uintptr_t>(Wt) % 16 == 0;
+  a.M = Co; a.N = g.Ho * g.Wo; a.K = Ci * kh * kw;
+  finish_tiles(a, dtype);
+  return launch_conv<CONV_FWD>(a, dtype, (unsigned)(B * Nb), as_stream(stream));
+}
+
+size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride,
+                                               int pad, int dtype) {
+  ConvGeom g;
+  if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
+  ConvArgs a = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
+  a.M = Co; a.N = Ci * kh * kw; a.K = g.Ho * g.Wo; a.S = Nb;
+  finish_tiles(a, dtype);
+  const int sp = dw_splits(a);
+  return sp > 1 ? (size_t)sp * B * (size_t)a.M * a.N * sizeof(float) : 0;
+}
+
+int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype,
+                            const void* X, const void* Wt, const void* dY, void* dX, float* dW, float* dbias,
+                            void* workspace, size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  int rc = check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g);
+  if (rc != HFTA_OK) return rc;
+  if (!dY || (dX && !Wt) || (dW && !X)) return HFTA_EINVAL;
+  hipStream_t st = as_stream(stream);
+  ConvArgs w = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
+  if (dW) {
+    w.X = X; w.dY = dY; w.Out = dW;
+    w.a_vec = reinterpret_cast<uintptr_t>(dY) % 16 == 0;
+    w.M = Co; w.N = Ci * kh * kw; w.K = g.Ho * g.Wo; w.S = Nb;
+    finish_tiles(w, dtype);
+    w.splits = dw_splits(w);
+    if (w.splits > 1) {
+      const size_t need = (size_t)w.splits * B * (size_t)w.M * w.N * sizeof(float);
+      if (!workspace || ws_bytes < need) return HFTA_EWORKSPACE;
+      w.partial = reinterpret_cast<float*>(workspace);
+    }
+  }
+  if (dX) {
+    ConvArgs a = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
+    a.Wt = Wt; a.dY = dY; a.Out = dX;
+    a.a_vec = reinterpret_cast<uintptr_t>(Wt) % 16 == 0;
+    a.M = Ci; a.N = H * W; a.K = Co * kh * kw;
+    finish_tiles(a, dtype);
+    rc = launch_conv<CONV_DX>(a, dtype, (unsigned)(B * Nb), st);
+    if (rc != HFTA_OK) return rc;
+  }
+  if (dW) {
+    rc = launch_conv<CONV_DW>(w, dtype, (unsigned)(B * w.splits), st);
+    if (rc != HFTA_OK) return rc;
+    if (w.splits > 1) {
+      const int64_t count = (int64_t)B * w.M * w.N;
+      hipLaunchKernelGGL(conv_splitk_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+                         (const float*)w.partial, dW, count, w.splits);
+      if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+    }
+  }
+  if (dbias) {
+    const int64_t HoWo = (int64_t)g.Ho * g.Wo;
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(conv_dbias_kernel<bf16_raw>, dim3((unsigned)(B * Co)), dim3(256), 0, st, (const bf16_raw*)dY, dbias,
+                         Nb, B * Co, HoWo);
+    else
+      hipLaunchKernelGGL(conv_dbias_kernel<float>, dim3((unsigned)(B * Co)), dim3(256), 0, st, (const float*)dY, dbias, Nb,
+                         B * Co, HoWo);
+    return launch_status();
+  }
+  return HFTA_OK;
+}
+
+}  // extern "C"

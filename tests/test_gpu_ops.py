@@ -365,3 +365,74 @@ def test_losses(hb, dtype):
     rl, rdp = oa.bce_logits(B, p, tb)
     check(host(loss), rl, 1e-5, "bce loss")
     check(host(dp), rdp, TOL[dtype], "dlogits(bce)")
+
+
+# ------------------------------------------------------------------ grouped Conv2d / ConvTranspose2d
+CONV_CASES = [
+    # B, Nb, Ci, Co, H, k, s, p
+    (3, 2, 5, 7, 12, 4, 2, 1),      # ragged channels
+    (2, 2, 3, 64, 16, 4, 2, 1),     # first discriminator layer shape (3 -> 64)
+    (2, 3, 16, 130, 32, 4, 2, 1),   # two row tiles, two pixel tiles
+    (2, 4, 64, 1, 4, 4, 1, 0),      # last discriminator layer: 4x4 -> 1x1
+    (2, 2, 6, 9, 9, 3, 1, 1),       # generic 3x3
+    (1, 1, 8, 8, 10, 1, 1, 0),      # k = 1
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,Ci,Co,H,k,s,p", CONV_CASES)
+def test_conv2d_grouped(hb, dtype, B, Nb, Ci, Co, H, k, s, p):
+    print(f"conv2d {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} H={H} k={k} s={s} p={p}", flush=True)
+    Wd = H + 2 if k > 1 and s == 1 and H > 4 else H
+    x = hi.normal(101, (Nb, B * Ci, H, Wd), dtype)
+    w = hi.normal(102, (B * Co, Ci, k, k), dtype, 1.0 / np.sqrt(Ci * k * k))
+    b = hi.normal(103, (B * Co,), dtype)
+    ry = oa.conv2d_fwd(B, x, w, b, s, p)
+    Ho, Wo = ry.shape[2], ry.shape[3]
+    dy = hi.normal(104, ry.shape, dtype)
+    X, W, Bi, dY = dev(x, dtype), dev(w, dtype), dev(b, dtype), dev(dy, dtype)
+    Y = empty(ry.shape, dtype)
+    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, Bi, Y)
+    check(host(Y), ry, TOL[dtype], "Y")
+    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, None, Y, hb.ACT_LEAKY, 0.2)
+    check(host(Y), oops.act_fwd(oa.conv2d_fwd(B, x, w, None, s, p), oops.ACT_LEAKY, 0.2), TOL[dtype], "leaky(Y)")
+    dX = empty(x.shape, dtype)
+    dW = empty(w.shape, torch.float32)
+    db = empty((B * Co,), torch.float32)
+    nws = hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype])
+    ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
+    hb.conv2d_grouped_bwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, dY, dX, dW, db, ws)
+    rdx, rdw, rdb = oa.conv2d_bwd(B, x, w, dy, s, p)
+    check(host(dX), rdx, TOL[dtype], "dX")
+    check(host(dW), rdw, f32_tol(dtype), "dW")
+    check(host(db), rdb, f32_tol(dtype), "dbias")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,Cx,Cy,H,k,s,p", [(3, 2, 10, 6, 4, 4, 2, 1), (2, 3, 20, 12, 1, 4, 1, 0), (2, 2, 8, 3, 8, 4, 2, 1)])
+def test_convT2d_through_conv_entry_points(hb, dtype, B, Nb, Cx, Cy, H, k, s, p):
+    """Fused ConvTranspose2d: forward = the data-gradient form of the grouped conv, its input
+    gradient = the forward form, its weight gradient = the weight-gradient form with X and dY
+    exchanged (weights [B*Cx, Cy, kh, kw] are read as conv weights [B*Co=Cx, Ci=Cy, kh, kw])."""
+    x = hi.normal(111, (Nb, B * Cx, H, H), dtype)
+    w = hi.normal(112, (B * Cx, Cy, k, k), dtype, 1.0 / np.sqrt(Cx * 4))
+    ry = oa.convT2d_fwd(B, x, w, None, s, p)
+    Ho = ry.shape[2]
+    dy = hi.normal(113, ry.shape, dtype)
+    X, W, dY = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
+    Y = empty(ry.shape, dtype)
+    conv = (B, Nb, Cy, Cx, Ho, Ho, k, k, s, p, DT[dtype])     # the conv whose input is ConvT's output
+    hb.conv2d_grouped_bwd(*conv, None, W, X, Y, None, None, None)
+    check(host(Y), ry, TOL[dtype], "convT fwd")
+    bias = hi.normal(114, (B * Cy,), dtype)
+    hb.bias_act_nchw(Nb, B * Cy, Ho * Ho, DT[dtype], Y, dev(bias, dtype), hb.ACT_TANH, 0.0)
+    check(host(Y), np.tanh(oa.convT2d_fwd(B, x, w, bias, s, p)), TOL[dtype], "tanh(convT + bias)")
+    rdx, rdw, _ = oa.convT2d_bwd(B, x, w, dy, s, p)
+    dX = empty(x.shape, dtype)
+    hb.conv2d_grouped_fwd(*conv, dY, W, None, dX)
+    check(host(dX), rdx, TOL[dtype], "convT dX")
+    dW = empty(w.shape, torch.float32)
+    nws = hb.conv2d_grouped_bwd_workspace_bytes(*conv)
+    ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
+    hb.conv2d_grouped_bwd(*conv, dY, None, X, None, dW, None, ws)
+    check(host(dW), rdw, f32_tol(dtype), "convT dW")

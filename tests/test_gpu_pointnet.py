@@ -1,0 +1,247 @@
+"""Whole-step parity: the fused PointNet-cls array on the GPU against B separate
+unfused oracle runs (the paper's defining equivalence), forward + backward +
+Adam, fp32 and bf16."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import hfta_inputs as hi
+from oracle import pointnet as opn
+
+pytestmark = pytest.mark.gpu
+
+# A free-running chain accumulates the per-operator bound (1e-5 fp32, 2e-2 bf16) about
+# linearly in the number of library calls it passes through; norm-wise per tensor and model.
+CHAIN_TOL = {"f32": 2e-4, "bf16": 6e-2}
+
+
+def chain_tol(spec):
+    nconv, nfc = len(spec.conv) - 1, len(spec.fc) - 1
+    calls = 4 * nconv + 2 + 2 * nfc + 1 + (2 * (nfc - 1) if spec.fc_bn else (nfc - 1)) + (2 if spec.dropout_p else 0)
+    per_op = 1e-5 if spec.dtype == "f32" else 2e-2
+    return per_op * calls if spec.dtype == "f32" else 6e-2
+
+
+def zero_grad_param(spec, name):
+    """Biases that feed a BatchNorm have a mathematically zero gradient (BatchNorm
+    removes the channel mean), so their computed gradient is rounding noise."""
+    if name.startswith("conv") and name.endswith(".b") and ".bn." not in name:
+        return True
+    if name.startswith("fc") and name.endswith(".b") and ".bn." not in name and spec.fc_bn:
+        return int(name[2]) < len(spec.fc) - 2
+    # With a BatchNorm after the first head layer, sum_n d(pooled)[n, c] = 0 exactly (the BatchNorm
+    # backward has zero batch sum and the Linear before it is linear), so the shift of the last
+    # per-point BatchNorm only collects a gradient from the rare channels whose maximum is clipped
+    # by the ReLU: its gradient is rounding noise as well.
+    if spec.fc_bn and name == f"conv{len(spec.conv) - 2}.bn.b":
+        return True
+    return False
+
+
+def run_case(spec, steps=1):
+    from paper_2102_02344_amd.arrays import FusedPointNetCls
+    inp = hi.pointnet_cls_inputs(spec)
+    arr = FusedPointNetCls(spec, inp)
+    states = [opn.init_state(inp["params"][b]) for b in range(spec.B)]
+    tol = chain_tol(spec)
+    for t in range(1, steps + 1):
+        print(f"{spec.name}: step {t}", flush=True)
+        outs = opn.array_train_step(spec, states, inp, t)
+        arr.forward_backward()
+        torch.cuda.synchronize()
+        loss = arr.loss.cpu().numpy()
+        idx = arr.pool_idx.cpu().numpy()
+        pooled = arr.pooled.float().cpu().numpy()
+        flips = 0
+        for b in range(spec.B):
+            assert abs(loss[b] - outs[b]["loss"]) <= tol * abs(outs[b]["loss"]), (b, loss[b], outs[b]["loss"])
+            # argmax after a float chain: a mismatch is only legitimate at a near-tie of the maximum
+            mism = idx[b] != outs[b]["pool_idx"]
+            flips += int(mism.sum())
+            assert np.abs(pooled[b] - outs[b]["pooled"]).max() <= tol * max(np.abs(outs[b]["pooled"]).max(), 1e-30)
+            wmax = max(np.abs(outs[b]["grads"][n]).max() for n, _ in arr.shapes if n.endswith(".w"))
+            for name, _ in arr.shapes:
+                g = arr.param_host(arr.grad, name, b).astype(np.float64)
+                ref = outs[b]["grads"][name]
+                if zero_grad_param(spec, name):
+                    assert np.abs(g).max() <= 1e-2 * wmax and np.abs(ref).max() <= 1e-2 * wmax, name
+                    continue
+                err = np.abs(g - ref).max() / max(np.abs(ref).max(), 1e-30)
+                assert err <= tol, (name, b, err)
+        assert flips <= 0.02 * idx.size, flips
+        arr.adam()
+        torch.cuda.synchronize()
+        for b in range(spec.B):
+            lr = float(inp["lr"][b])
+            for name, _ in arr.shapes:
+                if zero_grad_param(spec, name):
+                    continue
+                th = arr.param_host(arr.theta, name, b).astype(np.float64)
+                ref = states[b]["theta"][name].astype(np.float64)
+                gref = outs[b]["grads"][name]
+                # Adam's step is ~lr*sign(g) early on: where the gradient itself is at noise level
+                # its sign is not determined, so compare where it is well above noise
+                ok = np.abs(gref) >= 1e-2 * np.abs(gref).max()
+                assert np.abs(th - ref)[ok].max() <= max(tol * np.abs(ref).max(), 10 * tol * lr * t), (name, b)
+                assert np.abs(th - ref).max() <= 2.5 * lr * t, (name, b)
+            for kname in states[b]["running"]:
+                C = states[b]["running"][kname].shape[0]
+                rg = arr.running[kname].view(spec.B, C)[b].cpu().numpy()
+                # from step 2 on the running mean carries the zero-gradient biases, which Adam moves
+                # by up to ~lr per step in a direction set by rounding noise on either side
+                slack = 2.5 * lr * (t - 1) if kname.endswith(".rm") else 0.0
+                np.testing.assert_allclose(rg, states[b]["running"][kname], rtol=tol, atol=tol * 1e-2 + slack)
+    return arr
+
+
+def in_place_probe(spec, seen):
+    """Checks every library call of a step against the oracle's operator applied to the
+    very tensors (bits) that call consumed on the GPU: wiring, strides and buffers of the
+    whole chain are covered at per-operator tolerance, without the chain's amplification."""
+    from oracle import array as oa
+    from oracle import ops as oops
+    from util import TOL, check
+    B = spec.B
+    tol = TOL[spec.dtype]
+    ftol = 1e-5 if spec.dtype == "f32" else 2e-4
+
+    def H(t):
+        return None if t is None else (t.cpu().numpy() if t.dtype in (torch.int32, torch.uint8)
+                                       else t.float().cpu().numpy().astype(np.float64))
+
+    def cancel(kw, mean, invstd, weight=None):
+        """fp32 rounding of (x - mean) and of the stored mean, amplified by gamma*invstd: the
+        operator's own conditioning when a channel's |mean| is large against its spread."""
+        x, g = H(kw["x"]), np.abs(H(kw["g"]).reshape(-1))
+        amp = g * invstd * (1.0 if weight is None else weight * invstd)
+        if kw["layout"] == "conv":
+            return 4 * 2.0 ** -24 * amp[None, :, None] * (np.abs(x) + np.abs(mean)[None, :, None])
+        C = x.shape[2]
+        return 4 * 2.0 ** -24 * amp.reshape(B, 1, C) * (np.abs(x) + np.abs(mean).reshape(B, 1, C))
+
+    def probe(op, **kw):
+        torch.cuda.synchronize()
+        seen.append(op)
+        lay = kw.get("layer", "")
+        if op == "conv1x1_fwd":
+            Co = kw["y"].shape[1] // B
+            w = H(kw["w"]).reshape(B * Co, -1)
+            check(H(kw["y"]), oa.conv1x1_fwd(B, H(kw["x"]), w, H(kw["b"])), tol, f"{lay} fwd")
+        elif op == "bn_fwd":
+            y, mean, invstd, _, _ = oa.bn_fwd(B, H(kw["x"]), H(kw["g"]), H(kw["b"]), 1e-5, 0.1, None, None, kw["layout"])
+            check(H(kw["y"]), oops.act_fwd(y, oops.ACT_RELU), tol, f"{lay} bn", cancel(kw, mean, invstd))
+            check(H(kw["mean"]), mean, 1e-5, f"{lay} bn mean")
+            check(H(kw["invstd"]), invstd, 1e-5, f"{lay} bn invstd")
+        elif op == "maxpool_points":
+            v, idx = oa.maxpool_points_fwd(B, H(kw["x"]))
+            Nb, C = v.shape[0], v.shape[1] // B
+            assert np.array_equal(H(kw["idx"]), idx.reshape(Nb, B, C).transpose(1, 0, 2))
+            assert np.array_equal(H(kw["v"]), v.reshape(Nb, B, C).transpose(1, 0, 2))
+        elif op == "linear_fwd":
+            Fx = kw["x"].shape[2]
+            y = oa.linear_fwd(B, H(kw["x"]), H(kw["w"]).reshape(B, Fx, -1), H(kw["b"]).reshape(B, -1))
+            check(H(kw["y"]), oops.act_fwd(y, oops.ACT_RELU) if kw["act"] else y, tol, f"{lay} fwd")
+        elif op == "dropout":
+            check(H(kw["y"]), oops.dropout_fwd(H(kw["x"]), H(kw["mask"]), spec.dropout_p), tol, "dropout")
+        elif op == "softmax_xent":
+            loss, d = oa.softmax_xent(B, H(kw["logits"]), H(kw["labels"]))
+            check(H(kw["loss"]), loss, 1e-5, "loss")
+            check(H(kw["d"]), d, tol, "dlogits")
+        elif op == "relu_bwd_from_output":
+            check(H(kw["dx"]), oops.act_bwd(H(kw["y"]), H(kw["dy"]), oops.ACT_RELU), tol, "relu bwd")
+        elif op == "bn_bwd":
+            x, g, b = H(kw["x"]), H(kw["g"]), H(kw["b"])
+            y = oa.bn_fwd(B, x, g, b, 1e-5, 0.1, None, None, kw["layout"])[0]
+            dy = oops.act_bwd(y, H(kw["dy"]), oops.ACT_RELU)
+            dx, dg, db = oa.bn_bwd(B, x, dy, g, H(kw["mean"]), H(kw["invstd"]), kw["layout"])
+            mg = np.abs(dg) / (dy.size / dg.size)
+            check(H(kw["dx"]), dx, tol, f"{lay} bn dx", cancel(kw, H(kw["mean"]), H(kw["invstd"]), mg))
+            # reductions of signed terms: bound relative to the sum of magnitudes they add up
+            for got, ref, terms, nm in ((H(kw["dg"]), dg, None, "dgamma"), (H(kw["db"]), db, None, "dbeta")):
+                scale = max(np.abs(ref).max(), np.abs(dy).sum() / ref.size * 1e-3)
+                assert np.abs(got.reshape(-1) - ref).max() <= ftol * 10 * scale, f"{lay} bn {nm}"
+        elif op == "linear_bwd":
+            Fx = kw["x"].shape[2]
+            dx, dw, db = oa.linear_bwd(B, H(kw["x"]), H(kw["w"]).reshape(B, Fx, -1), H(kw["dy"]))
+            check(H(kw["dx"]), dx, tol, f"{lay} dX")
+            check(H(kw["dw"]).reshape(dw.shape), dw, ftol, f"{lay} dW")
+            sc = np.abs(H(kw["dy"])).sum(axis=1).max()
+            assert np.abs(H(kw["db"]).reshape(db.shape) - db).max() <= ftol * sc, f"{lay} dbias"
+        elif op == "maxpool_points_bwd":
+            dv, idx = H(kw["dv"]), H(kw["idx"])
+            Bn, Nb, C = dv.shape
+            ref = oa.maxpool_points_bwd(B, dv.transpose(1, 0, 2).reshape(Nb, B * C),
+                                        idx.transpose(1, 0, 2).reshape(Nb, B * C), kw["dx"].shape[2])
+            assert np.array_equal(H(kw["dx"]), ref)
+        elif op == "conv1x1_bwd":
+            Co = kw["dy"].shape[1] // B
+            w = H(kw["w"]).reshape(B * Co, -1)
+            dx, dw, db = oa.conv1x1_bwd(B, H(kw["x"]), w, H(kw["dy"]))
+            if kw["dx"] is not None:
+                check(H(kw["dx"]), dx, tol, f"{lay} dX")
+            check(H(kw["dw"]).reshape(dw.shape), dw, ftol, f"{lay} dW")
+            sc = np.abs(H(kw["dy"])).sum(axis=(0, 2)).max()
+            assert np.abs(H(kw["db"]) - db).max() <= ftol * sc, f"{lay} dbias"
+        else:
+            raise AssertionError(op)
+    return probe
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_c1_every_call_in_place(dtype):
+    """The headline config's layer list (reduced batch and points so the oracle finishes in
+    seconds; L = 500 is not a multiple of the 128-wide tile): every call of one step checked in place."""
+    from paper_2102_02344_amd.arrays import FusedPointNetCls
+    spec = hi.spec_c1(B=3, Nb=4, L=500, dtype=dtype)
+    inp = hi.pointnet_cls_inputs(spec)
+    arr = FusedPointNetCls(spec, inp)
+    seen = []
+    arr.forward_backward(in_place_probe(spec, seen))
+    assert len(seen) == 5 * 2 + 1 + 3 + 2 + 1 + 1 + 1 + 2 + 3 + 1 + 5 * 2
+    # forward results of the free-running chain stay close to the oracle's free-running chain
+    states = [opn.init_state(inp["params"][b]) for b in range(spec.B)]
+    outs = opn.array_train_step(spec, states, inp, 1)
+    loss = arr.loss.cpu().numpy()
+    for b in range(spec.B):
+        assert abs(loss[b] - outs[b]["loss"]) <= CHAIN_TOL[dtype] * abs(outs[b]["loss"])
+
+
+def test_c0_fp32_full_config_two_steps():
+    run_case(hi.spec_c0(), steps=2)
+
+
+def test_c1_fp32_reduced_ragged():
+    # batch 8: a BatchNorm over 3 samples is too ill-conditioned (1/std up to 316) for a chain bound
+    run_case(dataclasses.replace(hi.spec_c1(B=2, Nb=8, L=250, dtype="f32"), name="c1_f32_ragged"), steps=1)
+
+
+def test_fused_equals_serial_B1_on_gpu():
+    """Model i of the fused array equals that model run alone through the library with B = 1."""
+    from paper_2102_02344_amd.arrays import FusedPointNetCls
+    spec = hi.spec_c1(B=3, Nb=4, L=500)
+    inp = hi.pointnet_cls_inputs(spec)
+    arr = FusedPointNetCls(spec, inp)
+    arr.train_step()
+    torch.cuda.synchronize()
+    for b in range(spec.B):
+        s1 = dataclasses.replace(spec, B=1)
+        i1 = dict(inp)
+        i1["points"] = np.ascontiguousarray(inp["points"][:, 3 * b:3 * b + 3])
+        i1["labels"] = inp["labels"][b:b + 1]
+        i1["params"] = inp["params"][b:b + 1]
+        i1["drop_mask"] = inp["drop_mask"][b:b + 1]
+        for k in ("lr", "beta1", "beta2", "eps", "wd"):
+            i1[k] = inp[k][b:b + 1]
+        one = FusedPointNetCls(s1, i1)
+        one.train_step()
+        torch.cuda.synchronize()
+        assert abs(one.loss[0].item() - arr.loss[b].item()) <= 1e-6 * abs(arr.loss[b].item()) + 1e-7
+        assert torch.equal(one.pool_idx[0], arr.pool_idx[b])
+        for name, _ in arr.shapes:
+            if zero_grad_param(spec, name):
+                continue
+            g1 = one.param_host(one.grad, name, 0)
+            gb = arr.param_host(arr.grad, name, b)
+            assert np.abs(g1 - gb).max() <= 1e-5 * max(np.abs(gb).max(), 1e-30), name
