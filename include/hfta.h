@@ -162,12 +162,15 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype,
  * the activation mask is recomputed from X and the saved statistics in fp32,
  * exactly as the forward computed it.
  *   dY: gradient w.r.t. the activated output; dX: gradient w.r.t. X (storage dtype);
- *   dgamma, dbeta: fp32 [B][C]. */
+ *   dgamma, dbeta: fp32 [B][C].
+ *   dx_sum (fp32 [B][C], NULL = skip): per-channel sum over (n, l) of dX as stored.  When X was
+ *   produced by a fused Linear / Conv with a bias, this IS that layer's bias gradient, obtained
+ *   without another pass over dX. */
 int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype,
                 const void* X, const int64_t xs[4], const void* dY, const int64_t dys[4],
                 const float* gamma, const float* beta,
                 const float* save_mean, const float* save_invstd,
-                void* dX, const int64_t dxs[4], float* dgamma, float* dbeta,
+                void* dX, const int64_t dxs[4], float* dgamma, float* dbeta, float* dx_sum,
                 int act, float act_slope, void* stream);
 
 /* ------------------------------------------------------------------------

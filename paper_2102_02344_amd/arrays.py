@@ -212,7 +212,7 @@ class FusedPointNetCls:
                     ls = (Nb * fy, fy, 1, 1)
                     hb.bn_bwd(B, Nb, fy, 1, dt, self.fz[i], ls, d, ls, self.master(k + ".bn.g"),
                               self.master(k + ".bn.b"), self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
-                              nd, ls, self.g(k + ".bn.g"), self.g(k + ".bn.b"), hb.ACT_RELU)
+                              nd, ls, self.g(k + ".bn.g"), self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.g(k + ".b"))
                     P("bn_bwd", layer=k, layout="linear", x=self.fz[i], dy=d.view(B, Nb, fy),
                       g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"],
                       invstd=self.saved[k + ".bn.invstd"], dx=nd.view(B, Nb, fy), dg=self.g(k + ".bn.g"),
@@ -228,7 +228,9 @@ class FusedPointNetCls:
             else:
                 hin = self.fh[i - 1]
             nd = self.fd[cur ^ 1][:B * Nb * fx]
-            hb.linear_bwd(B, Nb, fx, fy, dt, hin, self.w(k + ".w"), d, nd, self.g(k + ".w"), self.g(k + ".b"), self.ws)
+            # a bias that feeds a BatchNorm gets its gradient from that BatchNorm's backward (dx_sum)
+            own_db = self.g(k + ".b") if (last or not s.fc_bn) else None
+            hb.linear_bwd(B, Nb, fx, fy, dt, hin, self.w(k + ".w"), d, nd, self.g(k + ".w"), own_db, self.ws)
             P("linear_bwd", layer=k, x=hin, w=self.w(k + ".w"), dy=d.view(B, Nb, fy), dx=nd.view(B, Nb, fx),
               dw=self.g(k + ".w"), db=self.g(k + ".b"))
             d, cur = nd, cur ^ 1
@@ -247,14 +249,14 @@ class FusedPointNetCls:
             dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
             hb.bn_bwd(B, Nb, co, L, dt, self.z[i], cs, da, cs, self.master(k + ".bn.g"), self.master(k + ".bn.b"),
                       self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], dz, cs, self.g(k + ".bn.g"),
-                      self.g(k + ".bn.b"), hb.ACT_RELU)
+                      self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.g(k + ".b"))
             P("bn_bwd", layer=k, layout="conv", x=self.z[i], dy=da.view(Nb, B * co, L), g=self.master(k + ".bn.g"),
               b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
               dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"), db=self.g(k + ".bn.b"))
             xin = self.points if i == 0 else self.a[i - 1]
             dxin = None if i == 0 else self.dbuf[cur][:Nb * B * ci * L]
             hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), dz, cs,
-                           dxin, None if i == 0 else _cs(B, ci, L), self.g(k + ".w"), self.g(k + ".b"), self.ws)
+                           dxin, None if i == 0 else _cs(B, ci, L), self.g(k + ".w"), None, self.ws)
             P("conv1x1_bwd", layer=k, x=xin, w=self.w(k + ".w"), dy=dz.view(Nb, B * co, L),
               dx=None if i == 0 else dxin.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"))
             da = dxin

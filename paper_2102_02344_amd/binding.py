@@ -51,7 +51,7 @@ _SIGS = {
     "hfta_conv2d_grouped_bwd_workspace_bytes": (_sz, [_i] * 11),
     "hfta_conv2d_grouped_bwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_bn_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
-    "hfta_bn_bwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _i, _f, _p]),
+    "hfta_bn_bwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_maxpool_points": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p]),
     "hfta_maxpool_points_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _s4, _p, _s4, _p]),
     "hfta_adam_step": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
@@ -177,10 +177,10 @@ def bn_fwd(B, Nb, C_, L, dtype, X, xs, gamma, beta, eps, momentum, running_mean,
 
 
 def bn_bwd(B, Nb, C_, L, dtype, X, xs, dY, dys, gamma, beta, save_mean, save_invstd, dX, dxs, dgamma, dbeta,
-           act=ACT_NONE, act_slope=0.0, stream=None):
+           act=ACT_NONE, act_slope=0.0, dx_sum=None, stream=None):
     _check(_lib.hfta_bn_bwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(dY), _strides(dys), _ptr(gamma),
                             _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dX), _strides(dxs), _ptr(dgamma),
-                            _ptr(dbeta), act, act_slope, _stream(stream)), "hfta_bn_bwd")
+                            _ptr(dbeta), _ptr(dx_sum), act, act_slope, _stream(stream)), "hfta_bn_bwd")
 
 
 def maxpool_points(B, Nb, C_, L, dtype, X, xs, V, idx, vs, stream=None):

@@ -10,6 +10,7 @@
 //
 // Linear layout (L == 1, stride_c == 1, the table's [N, B, C] case): one thread
 // per channel, coalesced across channels, two passes over the Nb samples.
+#include <stdlib.h>
 #include "common.h"
 
 using namespace hfta;
@@ -39,6 +40,7 @@ __device__ __forceinline__ void store_vec(T* p, const float (&v)[VEC]) {
 }
 
 // block-wide sum of two values; result valid in every thread
+template <int NW>
 __device__ __forceinline__ void block_sum2(float& a, float& b, float (*sh)[2]) {
   a = wave_sum(a);
   b = wave_sum(b);
@@ -46,8 +48,13 @@ __device__ __forceinline__ void block_sum2(float& a, float& b, float (*sh)[2]) {
   __syncthreads();
   if ((threadIdx.x & 63) == 0) { sh[w][0] = a; sh[w][1] = b; }
   __syncthreads();
-  a = (sh[0][0] + sh[1][0]) + (sh[2][0] + sh[3][0]);
-  b = (sh[0][1] + sh[1][1]) + (sh[2][1] + sh[3][1]);
+  float ra = 0.f, rb = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; i += 4) {          // fixed order, pairwise within groups of four waves
+    ra += (sh[i][0] + sh[i + 1][0]) + (sh[i + 2][0] + sh[i + 3][0]);
+    rb += (sh[i][1] + sh[i + 1][1]) + (sh[i + 2][1] + sh[i + 3][1]);
+  }
+  a = ra; b = rb;
 }
 
 __device__ __forceinline__ float act_grad(float pre, int act, float slope) {
@@ -65,9 +72,9 @@ struct BnFwdArgs {
   float eps, momentum, slope;
 };
 
-template <typename T, int VEC>
-__global__ __launch_bounds__(256) void bn_fwd_conv_kernel(BnFwdArgs p) {
-  __shared__ float sh[4][2];
+template <typename T, int VEC, int NT>
+__global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
+  __shared__ float sh[NT / 64][2];
   const int c = blockIdx.x, b = blockIdx.y;
   const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
   T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
@@ -75,14 +82,14 @@ __global__ __launch_bounds__(256) void bn_fwd_conv_kernel(BnFwdArgs p) {
   const int64_t total = (int64_t)p.Nb * chunks;
   const float shift = Elem<T>::load(x);
   float s1 = 0.f, s2 = 0.f;
-  for (int64_t i = threadIdx.x; i < total; i += 256) {
+  for (int64_t i = threadIdx.x; i < total; i += NT) {
     const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
     float v[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { const float d = v[e] - shift; s1 += d; s2 = fmaf(d, d, s2); }
   }
-  block_sum2(s1, s2, sh);
+  block_sum2<NT / 64>(s1, s2, sh);
   const float m = (float)p.Nb * (float)p.L;
   const float dm = s1 / m;
   const float mean = shift + dm;
@@ -100,13 +107,72 @@ __global__ __launch_bounds__(256) void bn_fwd_conv_kernel(BnFwdArgs p) {
       p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
     }
   }
-  for (int64_t i = threadIdx.x; i < total; i += 256) {
+  for (int64_t i = threadIdx.x; i < total; i += NT) {
     const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
     float v[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) v[e] = apply_act(fmaf(g, (v[e] - mean) * invstd, bt), p.act, p.slope);
     store_vec<T, VEC>(y + n * p.ysn + ch * VEC, v);
+  }
+}
+
+// Register-resident variant: a 1024-thread workgroup holds its whole channel (up to
+// MAXC * 1024 chunks of four elements) in registers between the statistics and the normalisation,
+// so the channel crosses HBM exactly once in and once out.
+template <typename T, int MAXC>
+__global__ __launch_bounds__(1024) void bn_fwd_conv_reg_kernel(BnFwdArgs p) {
+  constexpr int NT = 1024;
+  typedef typename Vec<T, 4>::type V;
+  __shared__ float sh[NT / 64][2];
+  const int c = blockIdx.x, b = blockIdx.y;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
+  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
+  const int chunks = p.L / 4;
+  const int total = p.Nb * chunks;
+  const float shift = Elem<T>::load(x);
+  V r[MAXC];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int i = threadIdx.x + j * NT;
+    if (i < total) {
+      const int n = i / chunks, ch = i - n * chunks;
+      r[j] = *reinterpret_cast<const V*>(x + n * p.xsn + ch * 4);
+      const T* e = reinterpret_cast<const T*>(&r[j]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { const float d = Elem<T>::to_f32(e[q]) - shift; s1 += d; s2 = fmaf(d, d, s2); }
+    }
+  }
+  block_sum2<NT / 64>(s1, s2, sh);
+  const float m = (float)p.Nb * (float)p.L;
+  const float dm = s1 / m;
+  const float mean = shift + dm;
+  float var = s2 / m - dm * dm;
+  var = var < 0.f ? 0.f : var;
+  const float invstd = 1.0f / sqrtf(var + p.eps);
+  const int k = b * p.C + c;
+  const float g = p.gamma[k], bt = p.beta[k];
+  if (threadIdx.x == 0) {
+    p.save_mean[k] = mean;
+    p.save_invstd[k] = invstd;
+    if (p.running_mean) {
+      const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
+      p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
+      p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int i = threadIdx.x + j * NT;
+    if (i < total) {
+      const int n = i / chunks, ch = i - n * chunks;
+      const T* e = reinterpret_cast<const T*>(&r[j]);
+      float v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = apply_act(fmaf(g, (Elem<T>::to_f32(e[q]) - mean) * invstd, bt), p.act, p.slope);
+      store_vec<T, 4>(y + n * p.ysn + ch * 4, v);
+    }
   }
 }
 
@@ -142,15 +208,15 @@ __global__ __launch_bounds__(256) void bn_fwd_linear_kernel(BnFwdArgs p) {
 struct BnBwdArgs {
   const void* X; const void* dY; void* dX;
   const float* gamma; const float* beta; const float* save_mean; const float* save_invstd;
-  float* dgamma; float* dbeta;
+  float* dgamma; float* dbeta; float* dx_sum;
   int64_t xsb, xsn, xsc, dysb, dysn, dysc, dxsb, dxsn, dxsc;
   int Nb, C, L, act;
   float slope;
 };
 
-template <typename T, int VEC>
-__global__ __launch_bounds__(256) void bn_bwd_conv_kernel(BnBwdArgs p) {
-  __shared__ float sh[4][2];
+template <typename T, int VEC, int NT>
+__global__ __launch_bounds__(NT) void bn_bwd_conv_kernel(BnBwdArgs p) {
+  __shared__ float sh[NT / 64][2];
   const int c = blockIdx.x, b = blockIdx.y, k = b * p.C + c;
   const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
   const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + c * p.dysc;
@@ -159,7 +225,7 @@ __global__ __launch_bounds__(256) void bn_bwd_conv_kernel(BnBwdArgs p) {
   const int chunks = p.L / VEC;
   const int64_t total = (int64_t)p.Nb * chunks;
   float s1 = 0.f, s2 = 0.f;
-  for (int64_t i = threadIdx.x; i < total; i += 256) {
+  for (int64_t i = threadIdx.x; i < total; i += NT) {
     const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
     float v[VEC], d[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
@@ -172,11 +238,12 @@ __global__ __launch_bounds__(256) void bn_bwd_conv_kernel(BnBwdArgs p) {
       s2 = fmaf(gr, xh, s2);
     }
   }
-  block_sum2(s1, s2, sh);
+  block_sum2<NT / 64>(s1, s2, sh);
   if (threadIdx.x == 0) { p.dbeta[k] = s1; p.dgamma[k] = s2; }
   const float m = (float)p.Nb * (float)p.L;
   const float mb = s1 / m, mg = s2 / m, sc = g * invstd;
-  for (int64_t i = threadIdx.x; i < total; i += 256) {
+  float s3 = 0.f;
+  for (int64_t i = threadIdx.x; i < total; i += NT) {
     const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
     float v[VEC], d[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
@@ -186,8 +253,76 @@ __global__ __launch_bounds__(256) void bn_bwd_conv_kernel(BnBwdArgs p) {
       const float xh = (v[e] - mean) * invstd;
       const float gr = d[e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
       v[e] = sc * (gr - mb - xh * mg);
+      s3 += Elem<T>::to_f32(Elem<T>::from_f32(v[e]));     // the value as it is stored
     }
     store_vec<T, VEC>(dx + n * p.dxsn + ch * VEC, v);
+  }
+  if (p.dx_sum) {
+    float dummy = 0.f;
+    block_sum2<NT / 64>(s3, dummy, sh);
+    if (threadIdx.x == 0) p.dx_sum[k] = s3;
+  }
+}
+
+template <typename T, int MAXC>
+__global__ __launch_bounds__(1024) void bn_bwd_conv_reg_kernel(BnBwdArgs p) {
+  constexpr int NT = 1024;
+  typedef typename Vec<T, 4>::type V;
+  __shared__ float sh[NT / 64][2];
+  const int c = blockIdx.x, b = blockIdx.y, k = b * p.C + c;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
+  const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + c * p.dysc;
+  T* dx = reinterpret_cast<T*>(p.dX) + b * p.dxsb + c * p.dxsc;
+  const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
+  const int chunks = p.L / 4;
+  const int total = p.Nb * chunks;
+  V rx[MAXC], rd[MAXC];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int i = threadIdx.x + j * NT;
+    if (i < total) {
+      const int n = i / chunks, ch = i - n * chunks;
+      rx[j] = *reinterpret_cast<const V*>(x + n * p.xsn + ch * 4);
+      rd[j] = *reinterpret_cast<const V*>(dy + n * p.dysn + ch * 4);
+      const T* ex = reinterpret_cast<const T*>(&rx[j]);
+      const T* ed = reinterpret_cast<const T*>(&rd[j]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float xh = (Elem<T>::to_f32(ex[q]) - mean) * invstd;
+        const float gr = Elem<T>::to_f32(ed[q]) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+        s1 += gr;
+        s2 = fmaf(gr, xh, s2);
+      }
+    }
+  }
+  block_sum2<NT / 64>(s1, s2, sh);
+  if (threadIdx.x == 0) { p.dbeta[k] = s1; p.dgamma[k] = s2; }
+  const float m = (float)p.Nb * (float)p.L;
+  const float mb = s1 / m, mg = s2 / m, sc = g * invstd;
+  float s3 = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXC; ++j) {
+    const int i = threadIdx.x + j * NT;
+    if (i < total) {
+      const int n = i / chunks, ch = i - n * chunks;
+      const T* ex = reinterpret_cast<const T*>(&rx[j]);
+      const T* ed = reinterpret_cast<const T*>(&rd[j]);
+      float v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float xh = (Elem<T>::to_f32(ex[q]) - mean) * invstd;
+        const float gr = Elem<T>::to_f32(ed[q]) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+        v[q] = sc * (gr - mb - xh * mg);
+        s3 += Elem<T>::to_f32(Elem<T>::from_f32(v[q]));
+      }
+      store_vec<T, 4>(dx + n * p.dxsn + ch * 4, v);
+    }
+  }
+  if (p.dx_sum) {
+    float dummy = 0.f;
+    block_sum2<NT / 64>(s3, dummy, sh);
+    if (threadIdx.x == 0) p.dx_sum[k] = s3;
   }
 }
 
@@ -210,17 +345,38 @@ __global__ __launch_bounds__(256) void bn_bwd_linear_kernel(BnBwdArgs p) {
   p.dbeta[k] = s1;
   p.dgamma[k] = s2;
   const float m = (float)p.Nb, mb = s1 / m, mg = s2 / m, sc = g * invstd;
+  float s3 = 0.f;
   for (int n = 0; n < p.Nb; ++n) {
     const float xh = (Elem<T>::load(x + n * p.xsn) - mean) * invstd;
     const float gr = Elem<T>::load(dy + n * p.dysn) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
-    Elem<T>::store(dx + n * p.dxsn, sc * (gr - mb - xh * mg));
+    const T o = Elem<T>::from_f32(sc * (gr - mb - xh * mg));
+    dx[n * p.dxsn] = o;
+    s3 += Elem<T>::to_f32(o);
   }
+  if (p.dx_sum) p.dx_sum[k] = s3;
 }
 
 bool vec_ok(const void* p, const int64_t* s, int L, int dtype) {
   const int es = (int)dtype_size(dtype);
   const size_t bytes = 4 * es;
   return L % 4 == 0 && reinterpret_cast<uintptr_t>(p) % bytes == 0 && s[0] % 4 == 0 && s[1] % 4 == 0 && s[2] % 4 == 0;
+}
+
+// Channels whose data is large get one 1024-thread workgroup each: at most two fit on a compute
+// unit, so the channels in flight (512 x channel bytes) stay within the 256 MB Infinity Cache and
+// the second pass of each channel is served from it instead of HBM.
+bool wide_block(int64_t channel_bytes) {
+  static const char* env = getenv("HFTA_BN_WIDE");          // experiment switch: 0 / 1 force
+  if (env) return env[0] == '1';
+  return channel_bytes >= 32 * 1024;
+}
+
+// The register-resident kernels cross HBM once per direction but serialise load, reduce and store
+// phases with one or two workgroups per compute unit; measured slower than the wide streaming
+// kernels at the PointNet shapes (1018 vs 774 us forward), so they are opt-in.
+bool reg_resident() {
+  static const char* env = getenv("HFTA_BN_REG");
+  return env && env[0] == '1';
 }
 
 int layout_kind(const int64_t* s, int L) {
@@ -257,20 +413,26 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   }
   dim3 grid((unsigned)C, (unsigned)B);
   const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
-  if (dtype == HFTA_BF16) {
-    if (v4) hipLaunchKernelGGL((bn_fwd_conv_kernel<bf16_raw, 4>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bn_fwd_conv_kernel<bf16_raw, 1>), grid, dim3(256), 0, st, a);
-  } else {
-    if (v4) hipLaunchKernelGGL((bn_fwd_conv_kernel<float, 4>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bn_fwd_conv_kernel<float, 1>), grid, dim3(256), 0, st, a);
+  const bool big = wide_block((int64_t)Nb * L * dtype_size(dtype));
+  const int64_t nchunks = (int64_t)Nb * (L / 4);
+  if (v4 && big && nchunks <= 20 * 1024 && reg_resident()) {
+    if (dtype == HFTA_BF16) hipLaunchKernelGGL((bn_fwd_conv_reg_kernel<bf16_raw, 20>), grid, dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL((bn_fwd_conv_reg_kernel<float, 20>), grid, dim3(1024), 0, st, a);
+    return launch_status();
   }
+#define HFTA_BN_FWD(T, V) \
+  do { if (big) hipLaunchKernelGGL((bn_fwd_conv_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a); \
+       else hipLaunchKernelGGL((bn_fwd_conv_kernel<T, V, 256>), grid, dim3(256), 0, st, a); } while (0)
+  if (dtype == HFTA_BF16) { if (v4) HFTA_BN_FWD(bf16_raw, 4); else HFTA_BN_FWD(bf16_raw, 1); }
+  else { if (v4) HFTA_BN_FWD(float, 4); else HFTA_BN_FWD(float, 1); }
+#undef HFTA_BN_FWD
   return launch_status();
 }
 
 int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const void* dY,
                 const int64_t dys[4], const float* gamma, const float* beta, const float* save_mean,
-                const float* save_invstd, void* dX, const int64_t dxs[4], float* dgamma, float* dbeta, int act,
-                float act_slope, void* stream) {
+                const float* save_invstd, void* dX, const int64_t dxs[4], float* dgamma, float* dbeta, float* dx_sum,
+                int act, float act_slope, void* stream) {
   if (B <= 0 || Nb <= 0 || C <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !dY || !dys || !gamma || !beta ||
       !save_mean || !save_invstd || !dX || !dxs || !dgamma || !dbeta)
     return HFTA_EINVAL;
@@ -279,7 +441,7 @@ int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   const bool lin = (L == 1 && xs[2] == 1 && dys[2] == 1 && dxs[2] == 1);
   const int kx = lin ? 2 : layout_kind(xs, L);
   if (kx == 0 || (!lin && (layout_kind(dys, L) != kx || layout_kind(dxs, L) != kx))) return HFTA_EUNSUPPORTED;
-  BnBwdArgs a{X, dY, dX, gamma, beta, save_mean, save_invstd, dgamma, dbeta,
+  BnBwdArgs a{X, dY, dX, gamma, beta, save_mean, save_invstd, dgamma, dbeta, dx_sum,
               xs[0], xs[1], xs[2], dys[0], dys[1], dys[2], dxs[0], dxs[1], dxs[2], Nb, C, L, act, act_slope};
   hipStream_t st = as_stream(stream);
   if (kx == 2) {
@@ -290,13 +452,19 @@ int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   }
   dim3 grid((unsigned)C, (unsigned)B);
   const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(dY, dys, L, dtype) && vec_ok(dX, dxs, L, dtype);
-  if (dtype == HFTA_BF16) {
-    if (v4) hipLaunchKernelGGL((bn_bwd_conv_kernel<bf16_raw, 4>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bn_bwd_conv_kernel<bf16_raw, 1>), grid, dim3(256), 0, st, a);
-  } else {
-    if (v4) hipLaunchKernelGGL((bn_bwd_conv_kernel<float, 4>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bn_bwd_conv_kernel<float, 1>), grid, dim3(256), 0, st, a);
+  const bool big = wide_block((int64_t)Nb * L * dtype_size(dtype));
+  const int64_t nchunks = (int64_t)Nb * (L / 4);
+  if (v4 && big && reg_resident() && ((dtype == HFTA_BF16 && nchunks <= 20 * 1024) || (dtype == HFTA_F32 && nchunks <= 10 * 1024))) {
+    if (dtype == HFTA_BF16) hipLaunchKernelGGL((bn_bwd_conv_reg_kernel<bf16_raw, 20>), grid, dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL((bn_bwd_conv_reg_kernel<float, 10>), grid, dim3(1024), 0, st, a);
+    return launch_status();
   }
+#define HFTA_BN_BWD(T, V) \
+  do { if (big) hipLaunchKernelGGL((bn_bwd_conv_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a); \
+       else hipLaunchKernelGGL((bn_bwd_conv_kernel<T, V, 256>), grid, dim3(256), 0, st, a); } while (0)
+  if (dtype == HFTA_BF16) { if (v4) HFTA_BN_BWD(bf16_raw, 4); else HFTA_BN_BWD(bf16_raw, 1); }
+  else { if (v4) HFTA_BN_BWD(float, 4); else HFTA_BN_BWD(float, 1); }
+#undef HFTA_BN_BWD
   return launch_status();
 }
 

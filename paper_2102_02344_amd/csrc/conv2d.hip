@@ -42,7 +42,7 @@ struct ConvArgs {
   int B, Nb, Ci, Co, H, W, Ho, Wo, kh, kw, stride, pad;
   int M, N, K, S;   // GEMM view; S = outer reduction segments (dW: Nb)
   int tiles_n, tiles_per_seg, total_tiles, splits;
-  int act, a_vec;
+  int act, a_vec, c_vec;
   float slope;
   FastDiv d_kw, d_khkw, d_wo, d_w;
 };
@@ -223,44 +223,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv_gemm_kernel(ConvArgs p) {
     }
   }
 
-  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
   if (MODE == CONV_DW) {
     // fp32 output [b][M][N] (contiguous), through the partial buffer when split
     float* base = p.splits > 1 ? p.partial + ((int64_t)split * p.B + b) * (int64_t)p.M * p.N
                                : reinterpret_cast<float*>(p.Out) + (int64_t)b * p.M * p.N;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int n = n0 + wn * 64 + j * 32 + col_l;
-        if (n >= p.N) continue;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-          if (m < p.M) base[(int64_t)m * p.N + n] = acc[i][j][v];
-        }
-      }
+    store_tile<float, T>(acc, &smem[0][0][0], base, p.N, p.M, p.N, m0, n0, nullptr, 0, HFTA_ACT_NONE, 0.f, p.c_vec, t);
     return;
   }
   // fwd: Y[n][b*Co + m][pix]; dX: dX[n][b*Ci + m][ipx]
   T* out = reinterpret_cast<T*>(p.Out) + (((int64_t)nimg * p.B + b) * p.M) * (int64_t)p.N;
   const T* bias = (MODE == CONV_FWD && p.bias) ? reinterpret_cast<const T*>(p.bias) + (int64_t)b * p.Co : nullptr;
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + col_l;
-      if (n >= p.N) continue;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-        if (m >= p.M) continue;
-        float x = acc[i][j][v];
-        if (bias) x += Elem<T>::load(bias + m);
-        if (MODE == CONV_FWD) x = apply_act(x, p.act, p.slope);
-        Elem<T>::store(out + (int64_t)m * p.N + n, x);
-      }
-    }
+  store_tile<T, T>(acc, &smem[0][0][0], out, p.N, p.M, p.N, m0, n0, bias, 1, MODE == CONV_FWD ? p.act : HFTA_ACT_NONE,
+                   p.slope, p.c_vec, t);
 }
 
 __global__ void conv_splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t count, int splits) {
@@ -331,8 +305,16 @@ int dw_splits(const ConvArgs& a) {
   return want < 1 ? 1 : (int)want;
 }
 
+int store_bytes(const void* p, int64_t n, int es) {
+  for (int w = 16; w >= 8; w >>= 1)
+    if (reinterpret_cast<uintptr_t>(p) % w == 0 && n % (w / es) == 0) return w;
+  return 0;
+}
+
 template <int MODE>
-int launch_conv(const ConvArgs& a, int dtype, unsigned gz, hipStream_t st) {
+int launch_conv(ConvArgs a, int dtype, unsigned gz, hipStream_t st) {
+  if (MODE == CONV_DW) a.c_vec = store_bytes(a.splits > 1 ? (const void*)a.partial : a.Out, a.N, 4);
+  else a.c_vec = store_bytes(a.Out, a.N, (int)dtype_size(dtype));
   dim3 grid((unsigned)(((a.M + GEMM_BM - 1) / GEMM_BM) * a.tiles_n), 1, gz);
   if (dtype == HFTA_BF16) hipLaunchKernelGGL((conv_gemm_kernel<bf16_raw, MODE>), grid, dim3(GEMM_THREADS), 0, st, a);
   else hipLaunchKernelGGL((conv_gemm_kernel<float, MODE>), grid, dim3(GEMM_THREADS), 0, st, a);

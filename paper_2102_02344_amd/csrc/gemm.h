@@ -58,7 +58,7 @@ struct GemmArgs {
   int64_t bias_g0, bias_g1;
   int M, N, K, S, G1;
   int tiles_n, tiles_per_seg, total_tiles, splits;
-  int a_vec, b_vec;
+  int a_vec, b_vec, c_vec, p_vec;
   int bias_mode, act;
   float slope;
 };
@@ -86,8 +86,12 @@ __device__ __forceinline__ void load_kc(uint4 (&q)[2], const T* base, int64_t ld
   for (int h = 0; h < 2; ++h) {
     const int r = row0 + (t >> 2) + 64 * h;
     const T* src = base + (int64_t)r * ld + k;
-    if (vec && r < rows && k + KG <= K) {
+    if (vec == 2 && r < rows && k + KG <= K) {
       q[h] = *reinterpret_cast<const uint4*>(src);
+    } else if (vec == 1 && r < rows && k + KG <= K) {     // rows only 8-byte aligned
+      const uint2 lo = *reinterpret_cast<const uint2*>(src);
+      const uint2 hi = *reinterpret_cast<const uint2*>(src + KG / 2);
+      q[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
     } else {
       T tmp[KG];
 #pragma unroll
@@ -167,6 +171,9 @@ template <> struct Stager<float, false> {
 };
 
 // ---- MFMA on one k-tile ---------------------------------------------------
+// The B fragment is passed as the MFMA's first operand, so the accumulators hold the
+// TRANSPOSED block: lane l owns row m = l % 32 and columns n = 8*(v/4) + 4*(l/32) + v%4 of each
+// 32x32 block, i.e. four consecutive n per group of four registers -- what a row-major store wants.
 template <typename T>
 __device__ __forceinline__ void mma_tile(f32x16_t (&acc)[2][2], const unsigned char* As,
                                          const unsigned char* Bs, int wm, int wn, int lane);
@@ -186,7 +193,7 @@ __device__ __forceinline__ void mma_tile<bf16_raw>(f32x16_t (&acc)[2][2], const 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
   }
 }
 template <>
@@ -205,11 +212,98 @@ __device__ __forceinline__ void mma_tile<float>(f32x16_t (&acc)[2][2], const uns
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].x, a[i].x, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].y, a[i].y, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].z, a[i].z, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[j].w, a[i].w, acc[i][j], 0, 0, 0);
       }
+  }
+}
+
+// ---- epilogue: accumulators -> LDS -> wide row-major global stores ------------
+// The 128x128 tile is staged through LDS (all 128 rows at once for 2-byte outputs, two passes of
+// 64 rows for 4-byte outputs) so that every global store is a 16-byte (or 8-byte, when the row
+// pitch only allows that) piece of a contiguous row segment.  Requires the k-loop's last barrier.
+constexpr int EPI_PITCH2 = 128 * 2 + 8;    // bytes, 2-byte outputs: 8-byte aligned rows
+constexpr int EPI_PITCH4 = 128 * 4 + 16;   // bytes, 4-byte outputs: 16-byte aligned rows
+
+template <typename OutT, typename BiasT>
+__device__ __forceinline__ void store_tile(f32x16_t (&acc)[2][2], unsigned char* lds, OutT* Cb, int64_t c_ld,
+                                           int M, int N, int m0, int n0, const BiasT* bias, int bias_mode,
+                                           int act, float slope, int c_vec, int t) {
+  constexpr int ES = sizeof(OutT);
+  constexpr int RP = ES == 2 ? 128 : 64;                 // rows per pass
+  constexpr int PITCH = ES == 2 ? EPI_PITCH2 : EPI_PITCH4;
+  constexpr int EPC = 16 / ES;                           // elements per 16-byte chunk
+  constexpr int CPR = 128 / EPC;                         // chunks per row
+  const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+  const int ml = lane & 31, nq = (lane >> 5) * 4;
+#pragma unroll
+  for (int pass = 0; pass < 128 / RP; ++pass) {
+    if (RP == 128 || wm == pass) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int rl = (RP == 128 ? wm * 64 : 0) + i * 32 + ml;
+        const int m = m0 + wm * 64 + i * 32 + ml;
+        float bm = 0.f;
+        if (bias && bias_mode == 1 && m < M) bm = Elem<BiasT>::load(bias + m);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int nl = wn * 64 + j * 32 + 8 * q + nq;
+            float x[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              x[e] = acc[i][j][4 * q + e] + bm;
+              if (bias && bias_mode == 2 && n0 + nl + e < N) x[e] += Elem<BiasT>::load(bias + n0 + nl + e);
+              x[e] = apply_act(x[e], act, slope);
+            }
+            unsigned char* dst = lds + rl * PITCH + nl * ES;
+            if (ES == 2) {
+              uint2 o;
+              o.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
+              o.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+              *reinterpret_cast<uint2*>(dst) = o;
+            } else {
+              *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+            }
+          }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < RP * CPR / GEMM_THREADS; ++it) {
+      const int id = t + GEMM_THREADS * it;
+      const int r = id / CPR, c = id % CPR;
+      const int m = m0 + pass * RP + r;
+      const int n = n0 + c * EPC;
+      if (m >= M || n >= N) continue;
+      const unsigned char* src = lds + r * PITCH + c * 16;
+      uint2 lo = *reinterpret_cast<const uint2*>(src);
+      uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
+      OutT* dst = Cb + (int64_t)m * c_ld + n;
+      if (c_vec == 16 && n + EPC <= N) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      } else if (c_vec >= 8 && n + EPC <= N) {
+        *reinterpret_cast<uint2*>(dst) = lo;
+        *reinterpret_cast<uint2*>(dst + EPC / 2) = hi;
+      } else if (c_vec >= 8 && n + EPC / 2 <= N) {
+        *reinterpret_cast<uint2*>(dst) = lo;
+        const OutT* e = reinterpret_cast<const OutT*>(&hi);
+#pragma unroll
+        for (int k = 0; k < EPC / 2; ++k)
+          if (n + EPC / 2 + k < N) dst[EPC / 2 + k] = e[k];
+      } else {
+        OutT e[EPC];
+        *reinterpret_cast<uint2*>(e) = lo;
+        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(e) + 8) = hi;
+#pragma unroll
+        for (int k = 0; k < EPC; ++k)
+          if (n + k < N) dst[k] = e[k];
+      }
+    }
+    if (pass + 1 < 128 / RP) __syncthreads();
   }
 }
 
@@ -268,44 +362,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs p) {
     }
   }
 
-  // epilogue: lane holds column (lane % 32) and rows 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 block
-  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
   if (p.splits > 1) {
-    float* Pb = p.partial + ((int64_t)split * gridDim.z / p.splits + g) * (int64_t)p.M * p.N;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int n = n0 + wn * 64 + j * 32 + col_l;
-        if (n >= p.N) continue;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-          if (m < p.M) Pb[(int64_t)m * p.N + n] = acc[i][j][v];
-        }
-      }
+    float* Pb = p.partial + ((int64_t)split * (gridDim.z / p.splits) + g) * (int64_t)p.M * p.N;
+    store_tile<float, T>(acc, &smem[0][0][0], Pb, p.N, p.M, p.N, m0, n0, nullptr, 0, HFTA_ACT_NONE, 0.f, p.p_vec, t);
     return;
   }
   OutT* Cb = reinterpret_cast<OutT*>(p.C) + g0 * p.c_g0 + g1 * p.c_g1;
   const T* bias = p.bias ? reinterpret_cast<const T*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + col_l;
-      if (n >= p.N) continue;
-      float bn = 0.f;
-      if (bias && p.bias_mode == 2) bn = Elem<T>::load(bias + n);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-        if (m >= p.M) continue;
-        float x = acc[i][j][v] + bn;
-        if (bias && p.bias_mode == 1) x += Elem<T>::load(bias + m);
-        x = apply_act(x, p.act, p.slope);
-        Elem<OutT>::store(Cb + (int64_t)m * p.c_ld + n, x);
-      }
-    }
+  store_tile<OutT, T>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t);
 }
 
 int gemm_pick_splits(const GemmDesc& d);

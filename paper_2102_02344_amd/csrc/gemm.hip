@@ -80,12 +80,27 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   // vector-load eligibility: every address the fast path forms must be aligned
   const int es = (int)dtype_size(d.dtype);
   const int kg = 16 / es, nv = 8 / es;
+  // 0: element-wise; 1: 8-byte loads; 2 (k-contiguous operands only): 16-byte loads
   auto ok = [&](const void* p, int64_t ld, int64_t ss, int64_t s0, int64_t s1, bool kc) {
-    const int q = kc ? kg : nv;
-    return aligned_to(p, kc ? 16 : 8) && ld % q == 0 && ss % q == 0 && s0 % q == 0 && s1 % q == 0;
+    auto al = [&](int q, size_t bytes) {
+      return aligned_to(p, bytes) && ld % q == 0 && ss % q == 0 && s0 % q == 0 && s1 % q == 0;
+    };
+    if (kc && al(kg, 16)) return 2;
+    return al(nv, 8) ? 1 : 0;
   };
   a.a_vec = ok(d.A, d.a_ld, d.a_ss, d.a_g0, d.a_g1, d.a_kc);
   a.b_vec = ok(d.Bm, d.b_ld, d.b_ss, d.b_g0, d.b_g1, d.b_kc);
+  // widest store (bytes) every row start of C / of the partial buffer is aligned to
+  const int oes = (d.out_f32 || splits > 1) ? 4 : es;
+  auto store_bytes = [&](const void* p, int64_t ld, int64_t s0, int64_t s1) {
+    for (int w = 16; w >= 8; w >>= 1) {
+      const int q = w / oes;
+      if (aligned_to(p, w) && ld % q == 0 && s0 % q == 0 && s1 % q == 0) return w;
+    }
+    return 0;
+  };
+  a.c_vec = store_bytes(d.C, d.c_ld, d.c_g0, d.c_g1);
+  a.p_vec = splits > 1 ? store_bytes(d.partial, d.N, (int64_t)d.M * d.N, 0) : 0;
 
   const int tiles_m = (d.M + GEMM_BM - 1) / GEMM_BM;
   dim3 grid((unsigned)(tiles_m * a.tiles_n), 1, (unsigned)(G * splits));

@@ -158,7 +158,11 @@ def test_bn_conv_layout(hb, dtype, B, Nb, C, L, act):
     check(host(RV), nrv, 1e-5, "running_var")
     dX = empty(x.shape, dtype)
     dG, dB = empty((B * C,), torch.float32), empty((B * C,), torch.float32)
-    hb.bn_bwd(B, Nb, C, L, DT[dtype], X, s, dY, s, G, Bt, SM, SI, dX, s, dG, dB, act, 0.2)
+    DS = empty((B * C,), torch.float32)
+    hb.bn_bwd(B, Nb, C, L, DT[dtype], X, s, dY, s, G, Bt, SM, SI, dX, s, dG, dB, act, 0.2, DS)
+    # dx_sum is the per-channel sum of dX as stored (the producer layer's bias gradient)
+    gdx = host(dX)
+    assert np.abs(host(DS) - gdx.sum(axis=(0, 2))).max() <= 1e-5 * np.abs(gdx).sum(axis=(0, 2)).max()
     # the oracle takes the activation mask from its own float64 pre-activation; elements whose
     # pre-activation is within rounding of zero may legitimately take the other branch in fp32
     knife = np.abs(ry) < 1e-5 * (np.abs(ry - bt[None, :, None]) + np.abs(bt)[None, :, None])
@@ -186,7 +190,9 @@ def test_bn_linear_layout_and_independence(hb, dtype):
     check(host(SM).reshape(-1), rmean, 1e-5, "mean")
     dX = empty(x.shape, dtype)
     dG, dB = empty((B, C), torch.float32), empty((B, C), torch.float32)
-    hb.bn_bwd(B, Nb, C, 1, DT[dtype], X, s, dY, s, G, Bt, SM, SI, dX, s, dG, dB, hb.ACT_RELU, 0.0)
+    DS = empty((B, C), torch.float32)
+    hb.bn_bwd(B, Nb, C, 1, DT[dtype], X, s, dY, s, G, Bt, SM, SI, dX, s, dG, dB, hb.ACT_RELU, 0.0, DS)
+    assert np.abs(host(DS) - host(dX).sum(axis=1)).max() <= 1e-5 * np.abs(host(dX)).sum(axis=1).max()
     rdx, rdg, rdb = oa.bn_bwd(B, x, oops.act_bwd(ry, dy, oops.ACT_RELU), g, rmean, rinv, "linear")
     check(host(dX), rdx, TOL[dtype], "dX")
     check(host(dG).reshape(-1), rdg, f32_tol(dtype), "dgamma")
