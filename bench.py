@@ -34,7 +34,7 @@ class Tracer:
     by HIP events on the stream they launch on (torch's current stream)."""
 
     SINGLE_KERNEL = ("conv1x1_fwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
-                     "adam_step_multi", "linear_fwd")
+                     "adam_step_multi", "linear_fwd", "bn_fwd_maxpool", "bn_bwd_maxpool")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -80,6 +80,8 @@ def kernel_label(name, a):
         return f"{name}_{lay}_kernel"
     if name in ("conv1x1_fwd", "linear_fwd"):
         return "gemm_kernel(fwd)"
+    if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
+        return name + "_kernel"
     return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",
             "adam_step_multi": "adam_multi_kernel"}[name]
 
@@ -92,6 +94,12 @@ def algorithmic_bytes(name, a):
     if name == "bn_bwd":
         B, Nb, C, L, dt = a[:5]
         return 3 * B * Nb * C * L * _es(dt)
+    if name == "bn_fwd_maxpool":
+        B, Nb, C, L, dt = a[:5]
+        return B * Nb * C * (L * _es(dt) + _es(dt) + 4)
+    if name == "bn_bwd_maxpool":
+        B, Nb, C, L, dt = a[:5]
+        return B * Nb * C * (2 * L * _es(dt) + _es(dt) + 4)
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         return (B * Nb * (Ci + Co) * L + B * Co * (Ci + 1)) * _es(dt)

@@ -191,6 +191,28 @@ int hfta_maxpool_points_bwd(int B, int Nb, int C, int L, int dtype,
                             void* dX, const int64_t dxs[4], void* stream);
 
 /* ------------------------------------------------------------------------
+ * BatchNorm + activation + point max-pool as one operator (PointNet's global feature is
+ * max_l act(BN(z))).  Same arguments as hfta_bn_fwd / hfta_maxpool_points; the activated
+ * tensor is never materialised.  Results are bit-identical to hfta_bn_fwd followed by
+ * hfta_maxpool_points: the maximum is taken over the activated values rounded to the storage
+ * dtype, lowest index on ties.  X needs stride_l == 1.
+ * Backward: dX = BatchNorm backward of the gradient that is dV[b,n,c] at l == idx[b,n,c] and 0
+ * elsewhere (equal to hfta_maxpool_points_bwd followed by hfta_bn_bwd up to fp32 summation
+ * order); indices outside [0, L) are clamped.  dx_sum as in hfta_bn_bwd.
+ * ---------------------------------------------------------------------- */
+int hfta_bn_fwd_maxpool(int B, int Nb, int C, int L, int dtype,
+                        const void* X, const int64_t xs[4], const float* gamma, const float* beta,
+                        float eps, float momentum, float* running_mean, float* running_var,
+                        float* save_mean, float* save_invstd,
+                        void* V, int32_t* idx, const int64_t vs[3], int act, float act_slope, void* stream);
+int hfta_bn_bwd_maxpool(int B, int Nb, int C, int L, int dtype,
+                        const void* X, const int64_t xs[4], const void* dV, const int32_t* idx,
+                        const int64_t vs[3], const float* gamma, const float* beta,
+                        const float* save_mean, const float* save_invstd,
+                        void* dX, const int64_t dxs[4], float* dgamma, float* dbeta, float* dx_sum,
+                        int act, float act_slope, void* stream);
+
+/* ------------------------------------------------------------------------
  * Fused Adam over the parameter arena of all B models (section "Our Proposal:
  * HFTA", paragraph on optimizers: a vector of per-model learning rates applied
  * to the concatenated gradients).

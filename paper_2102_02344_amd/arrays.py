@@ -87,7 +87,7 @@ class FusedPointNetCls:
         self.nconv = len(spec.conv) - 1
         self.nfc = len(spec.fc) - 1
         self.z = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:]]
-        self.a = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:]]
+        self.a = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:-1]]   # the last one is never stored
         cmax = max(spec.conv[1:])
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
         Cp = spec.conv[-1]
@@ -149,6 +149,19 @@ class FusedPointNetCls:
             hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
                            self.z[i], _cs(B, co, L))
             P("conv1x1_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
+            if i == self.nconv - 1:
+                # last per-point layer: BatchNorm + ReLU + max over points in one operator; the
+                # activated [Nb, B*C, L] tensor is never written
+                vs = (Nb * co, co, 1)
+                hb.bn_fwd_maxpool(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), self.master(k + ".bn.g"),
+                                  self.master(k + ".bn.b"), eps, mom, self.running[k + ".bn.rm"],
+                                  self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"],
+                                  self.saved[k + ".bn.invstd"], self.pooled, self.pool_idx, vs, hb.ACT_RELU)
+                P("bn_fwd_maxpool", layer=k, x=self.z[i], g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"),
+                  v=self.pooled, idx=self.pool_idx, mean=self.saved[k + ".bn.mean"],
+                  invstd=self.saved[k + ".bn.invstd"])
+                ci = co
+                break
             hb.bn_fwd(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), self.master(k + ".bn.g"), self.master(k + ".bn.b"),
                       eps, mom, self.running[k + ".bn.rm"], self.running[k + ".bn.rv"],
                       self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], self.a[i], _cs(B, co, L), hb.ACT_RELU)
@@ -156,9 +169,6 @@ class FusedPointNetCls:
               y=self.a[i], mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"])
             x, ci = self.a[i], co
         Cp = ci
-        vs = (Nb * Cp, Cp, 1)
-        hb.maxpool_points(B, Nb, Cp, L, dt, x, _cs(B, Cp, L), self.pooled, self.pool_idx, vs)
-        P("maxpool_points", x=x, v=self.pooled, idx=self.pool_idx)
         # head
         h, fx = self.pooled, s.fc[0]
         for i in range(self.nfc):
@@ -237,22 +247,31 @@ class FusedPointNetCls:
 
         # backward: pool and per-point MLP
         Cp = s.conv[-1]
-        n = Nb * B * Cp * L
-        da = self.dbuf[0][:n]
-        hb.maxpool_points_bwd(B, Nb, Cp, L, dt, d, self.pool_idx, (Nb * Cp, Cp, 1), da, _cs(B, Cp, L))
-        P("maxpool_points_bwd", dv=d.view(B, Nb, Cp), idx=self.pool_idx, dx=da.view(Nb, B * Cp, L))
+        dpool = d
+        da = None
         cur = 0
         for i in reversed(range(self.nconv)):
             ci, co = s.conv[i], s.conv[i + 1]
             k = f"conv{i}"
             cs = _cs(B, co, L)
             dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
-            hb.bn_bwd(B, Nb, co, L, dt, self.z[i], cs, da, cs, self.master(k + ".bn.g"), self.master(k + ".bn.b"),
-                      self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], dz, cs, self.g(k + ".bn.g"),
-                      self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.g(k + ".b"))
-            P("bn_bwd", layer=k, layout="conv", x=self.z[i], dy=da.view(Nb, B * co, L), g=self.master(k + ".bn.g"),
-              b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
-              dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"), db=self.g(k + ".bn.b"))
+            if i == self.nconv - 1:
+                hb.bn_bwd_maxpool(B, Nb, co, L, dt, self.z[i], cs, dpool, self.pool_idx, (Nb * co, co, 1),
+                                  self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],
+                                  self.saved[k + ".bn.invstd"], dz, cs, self.g(k + ".bn.g"), self.g(k + ".bn.b"),
+                                  hb.ACT_RELU, 0.0, self.g(k + ".b"))
+                P("bn_bwd_maxpool", layer=k, x=self.z[i], dv=dpool.view(B, Nb, co), idx=self.pool_idx,
+                  g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"],
+                  invstd=self.saved[k + ".bn.invstd"], dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"),
+                  db=self.g(k + ".bn.b"))
+            else:
+                hb.bn_bwd(B, Nb, co, L, dt, self.z[i], cs, da, cs, self.master(k + ".bn.g"), self.master(k + ".bn.b"),
+                          self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], dz, cs, self.g(k + ".bn.g"),
+                          self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.g(k + ".b"))
+                P("bn_bwd", layer=k, layout="conv", x=self.z[i], dy=da.view(Nb, B * co, L),
+                  g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"],
+                  invstd=self.saved[k + ".bn.invstd"], dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"),
+                  db=self.g(k + ".bn.b"))
             xin = self.points if i == 0 else self.a[i - 1]
             dxin = None if i == 0 else self.dbuf[cur][:Nb * B * ci * L]
             hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), dz, cs,

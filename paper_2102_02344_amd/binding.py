@@ -52,6 +52,8 @@ _SIGS = {
     "hfta_conv2d_grouped_bwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_bn_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
     "hfta_bn_bwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
+    "hfta_bn_fwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
+    "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_maxpool_points": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p]),
     "hfta_maxpool_points_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _s4, _p, _s4, _p]),
     "hfta_adam_step": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
@@ -181,6 +183,22 @@ def bn_bwd(B, Nb, C_, L, dtype, X, xs, dY, dys, gamma, beta, save_mean, save_inv
     _check(_lib.hfta_bn_bwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(dY), _strides(dys), _ptr(gamma),
                             _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dX), _strides(dxs), _ptr(dgamma),
                             _ptr(dbeta), _ptr(dx_sum), act, act_slope, _stream(stream)), "hfta_bn_bwd")
+
+
+def bn_fwd_maxpool(B, Nb, C_, L, dtype, X, xs, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
+                   save_invstd, V, idx, vs, act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_bn_fwd_maxpool(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(gamma), _ptr(beta), eps,
+                                    momentum, _ptr(running_mean), _ptr(running_var), _ptr(save_mean),
+                                    _ptr(save_invstd), _ptr(V), _ptr(idx), _strides(vs, 3), act, act_slope,
+                                    _stream(stream)), "hfta_bn_fwd_maxpool")
+
+
+def bn_bwd_maxpool(B, Nb, C_, L, dtype, X, xs, dV, idx, vs, gamma, beta, save_mean, save_invstd, dX, dxs, dgamma,
+                   dbeta, act=ACT_NONE, act_slope=0.0, dx_sum=None, stream=None):
+    _check(_lib.hfta_bn_bwd_maxpool(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(dV), _ptr(idx),
+                                    _strides(vs, 3), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd),
+                                    _ptr(dX), _strides(dxs), _ptr(dgamma), _ptr(dbeta), _ptr(dx_sum), act,
+                                    act_slope, _stream(stream)), "hfta_bn_bwd_maxpool")
 
 
 def maxpool_points(B, Nb, C_, L, dtype, X, xs, V, idx, vs, stream=None):

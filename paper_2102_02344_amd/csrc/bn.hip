@@ -11,57 +11,11 @@
 // Linear layout (L == 1, stride_c == 1, the table's [N, B, C] case): one thread
 // per channel, coalesced across channels, two passes over the Nb samples.
 #include <stdlib.h>
-#include "common.h"
+#include "bn_common.h"
 
 using namespace hfta;
 
 namespace {
-
-template <typename T, int VEC> struct Vec;
-template <> struct Vec<float, 4> { typedef float4 type; };
-template <> struct Vec<float, 1> { typedef float type; };
-template <> struct Vec<bf16_raw, 4> { typedef uint2 type; };
-template <> struct Vec<bf16_raw, 1> { typedef bf16_raw type; };
-
-template <typename T, int VEC>
-__device__ __forceinline__ void load_vec(const T* p, float (&v)[VEC]) {
-  typename Vec<T, VEC>::type raw = *reinterpret_cast<const typename Vec<T, VEC>::type*>(p);
-  const T* e = reinterpret_cast<const T*>(&raw);
-#pragma unroll
-  for (int i = 0; i < VEC; ++i) v[i] = Elem<T>::to_f32(e[i]);
-}
-template <typename T, int VEC>
-__device__ __forceinline__ void store_vec(T* p, const float (&v)[VEC]) {
-  typename Vec<T, VEC>::type raw;
-  T* e = reinterpret_cast<T*>(&raw);
-#pragma unroll
-  for (int i = 0; i < VEC; ++i) e[i] = Elem<T>::from_f32(v[i]);
-  *reinterpret_cast<typename Vec<T, VEC>::type*>(p) = raw;
-}
-
-// block-wide sum of two values; result valid in every thread
-template <int NW>
-__device__ __forceinline__ void block_sum2(float& a, float& b, float (*sh)[2]) {
-  a = wave_sum(a);
-  b = wave_sum(b);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) { sh[w][0] = a; sh[w][1] = b; }
-  __syncthreads();
-  float ra = 0.f, rb = 0.f;
-#pragma unroll
-  for (int i = 0; i < NW; i += 4) {          // fixed order, pairwise within groups of four waves
-    ra += (sh[i][0] + sh[i + 1][0]) + (sh[i + 2][0] + sh[i + 3][0]);
-    rb += (sh[i][1] + sh[i + 1][1]) + (sh[i + 2][1] + sh[i + 3][1]);
-  }
-  a = ra; b = rb;
-}
-
-__device__ __forceinline__ float act_grad(float pre, int act, float slope) {
-  if (act == HFTA_ACT_RELU) return pre > 0.f ? 1.f : 0.f;
-  if (act == HFTA_ACT_LEAKY) return pre > 0.f ? 1.f : slope;
-  return 1.f;
-}
 
 struct BnFwdArgs {
   const void* X; void* Y;
@@ -362,15 +316,6 @@ bool vec_ok(const void* p, const int64_t* s, int L, int dtype) {
   return L % 4 == 0 && reinterpret_cast<uintptr_t>(p) % bytes == 0 && s[0] % 4 == 0 && s[1] % 4 == 0 && s[2] % 4 == 0;
 }
 
-// Channels whose data is large get one 1024-thread workgroup each: at most two fit on a compute
-// unit, so the channels in flight (512 x channel bytes) stay within the 256 MB Infinity Cache and
-// the second pass of each channel is served from it instead of HBM.
-bool wide_block(int64_t channel_bytes) {
-  static const char* env = getenv("HFTA_BN_WIDE");          // experiment switch: 0 / 1 force
-  if (env) return env[0] == '1';
-  return channel_bytes >= 32 * 1024;
-}
-
 // The register-resident kernels cross HBM once per direction but serialise load, reduce and store
 // phases with one or two workgroups per compute unit; measured slower than the wide streaming
 // kernels at the PointNet shapes (1018 vs 774 us forward), so they are opt-in.
@@ -413,7 +358,7 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   }
   dim3 grid((unsigned)C, (unsigned)B);
   const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
-  const bool big = wide_block((int64_t)Nb * L * dtype_size(dtype));
+  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
   const int64_t nchunks = (int64_t)Nb * (L / 4);
   if (v4 && big && nchunks <= 20 * 1024 && reg_resident()) {
     if (dtype == HFTA_BF16) hipLaunchKernelGGL((bn_fwd_conv_reg_kernel<bf16_raw, 20>), grid, dim3(1024), 0, st, a);
@@ -452,7 +397,7 @@ int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   }
   dim3 grid((unsigned)C, (unsigned)B);
   const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(dY, dys, L, dtype) && vec_ok(dX, dxs, L, dtype);
-  const bool big = wide_block((int64_t)Nb * L * dtype_size(dtype));
+  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
   const int64_t nchunks = (int64_t)Nb * (L / 4);
   if (v4 && big && reg_resident() && ((dtype == HFTA_BF16 && nchunks <= 20 * 1024) || (dtype == HFTA_F32 && nchunks <= 10 * 1024))) {
     if (dtype == HFTA_BF16) hipLaunchKernelGGL((bn_bwd_conv_reg_kernel<bf16_raw, 20>), grid, dim3(1024), 0, st, a);

@@ -442,3 +442,61 @@ def test_convT2d_through_conv_entry_points(hb, dtype, B, Nb, Cx, Cy, H, k, s, p)
     ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
     hb.conv2d_grouped_bwd(*conv, dY, None, X, None, dW, None, ws)
     check(host(dW), rdw, f32_tol(dtype), "convT dW")
+
+
+# ------------------------------------------------------------------ BatchNorm + activation + point max-pool, fused
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,C,L", [(2, 9, 40, 500), (3, 4, 7, 250), (2, 32, 16, 2500), (1, 2, 3, 5)])
+def test_bn_maxpool_fused(hb, dtype, B, Nb, C, L):
+    print(f"bn+pool {dtype} B={B} Nb={Nb} C={C} L={L}", flush=True)
+    x = hi.snap(hi.normal(121, (Nb, B * C, L)) * 1.5 + 0.5, dtype)
+    g = (hi.normal(122, (B * C,)) * 0.5 + 1.0).astype(np.float32)
+    g[0] = -abs(g[0])                          # a negative scale: the maximum sits at the minimum of x
+    bt = (hi.normal(123, (B * C,)) * 0.3).astype(np.float32)
+    bt[1 % (B * C)] = -5.0                     # a channel that the ReLU clips everywhere: all-zero ties -> index 0
+    s = conv_strides(B, C, L)
+    vs = (Nb * C, C, 1)
+    X, G, Bt = dev(x, dtype), dev(g), dev(bt)
+    SM, SI = empty((B * C,), torch.float32), empty((B * C,), torch.float32)
+    V, I = empty((B, Nb, C), dtype), empty((B, Nb, C), torch.int32)
+    hb.bn_fwd_maxpool(B, Nb, C, L, DT[dtype], X, s, G, Bt, 1e-5, 0.1, None, None, SM, SI, V, I, vs, hb.ACT_RELU)
+    # (1) bit-identical to the two stand-alone operators
+    SM2, SI2 = empty((B * C,), torch.float32), empty((B * C,), torch.float32)
+    Y = empty(x.shape, dtype)
+    V2, I2 = empty((B, Nb, C), dtype), empty((B, Nb, C), torch.int32)
+    hb.bn_fwd(B, Nb, C, L, DT[dtype], X, s, G, Bt, 1e-5, 0.1, None, None, SM2, SI2, Y, s, hb.ACT_RELU)
+    hb.maxpool_points(B, Nb, C, L, DT[dtype], Y, s, V2, I2, vs)
+    assert torch.equal(SM, SM2) and torch.equal(SI, SI2)
+    assert torch.equal(I, I2) and torch.equal(V, V2)
+    # (2) against the oracle's composition; an index may differ only at a near-tie of the maximum
+    ry, rmean, rinv, _, _ = oa.bn_fwd(B, x, g, bt, 1e-5)
+    ya = oops.store(oops.act_fwd(ry, oops.ACT_RELU), dtype)
+    rv, ri = oa.maxpool_points_fwd(B, ya)
+    t3 = lambda a: a.reshape(Nb, B, C).transpose(1, 0, 2)
+    check(host(V), t3(rv), TOL[dtype], "pooled")
+    gi = I.cpu().numpy()
+    mism = gi != t3(ri)
+    if mism.any():
+        at = np.take_along_axis(ya, gi.transpose(1, 0, 2).reshape(Nb, B * C, 1).astype(np.int64), axis=2)[:, :, 0]
+        assert np.all(t3(at)[mism] >= t3(rv)[mism] - TOL[dtype] * (np.abs(t3(rv)[mism]) + np.abs(ya).max()))
+    assert mism.mean() <= 0.02
+    assert int(gi[(1 % (B * C)) // C, 0, (1 % (B * C)) % C]) == 0
+    # backward: equals scatter + BatchNorm backward
+    dv = hi.normal(124, (B, Nb, C), dtype)
+    dV = dev(dv, dtype)
+    dX = empty(x.shape, dtype)
+    dG, dB, DS = (empty((B * C,), torch.float32) for _ in range(3))
+    hb.bn_bwd_maxpool(B, Nb, C, L, DT[dtype], X, s, dV, I, vs, G, Bt, SM, SI, dX, s, dG, dB, hb.ACT_RELU, 0.0, DS)
+    dy = oa.maxpool_points_bwd(B, dv.transpose(1, 0, 2).reshape(Nb, B * C), gi.transpose(1, 0, 2).reshape(Nb, B * C), L)
+    gdy = oops.act_bwd(ry, dy, oops.ACT_RELU)
+    rdx, rdg, rdb = oa.bn_bwd(B, x, gdy, g, host(SM), host(SI))
+    check(host(dX), rdx, TOL[dtype], "dX")
+    sc = np.abs(dv).sum(axis=1).max()
+    assert np.abs(host(dG) - rdg).max() <= f32_tol(dtype) * max(np.abs(rdg).max(), sc * 1e-2), "dgamma"
+    assert np.abs(host(dB) - rdb).max() <= f32_tol(dtype) * max(np.abs(rdb).max(), sc * 1e-2), "dbeta"
+    dX2 = empty(x.shape, dtype)
+    dYd = empty(x.shape, dtype)
+    dG2, dB2 = empty((B * C,), torch.float32), empty((B * C,), torch.float32)
+    hb.maxpool_points_bwd(B, Nb, C, L, DT[dtype], dV, I, vs, dYd, s)
+    hb.bn_bwd(B, Nb, C, L, DT[dtype], X, s, dYd, s, G, Bt, SM, SI, dX2, s, dG2, dB2, hb.ACT_RELU, 0.0)
+    check(host(dX), host(dX2), 1e-5 if dtype == "f32" else 8e-3, "fused vs unfused dX")

@@ -134,6 +134,37 @@ def in_place_probe(spec, seen):
             check(H(kw["y"]), oops.act_fwd(y, oops.ACT_RELU), tol, f"{lay} bn", cancel(kw, mean, invstd))
             check(H(kw["mean"]), mean, 1e-5, f"{lay} bn mean")
             check(H(kw["invstd"]), invstd, 1e-5, f"{lay} bn invstd")
+        elif op == "bn_fwd_maxpool":
+            x = H(kw["x"])
+            y, mean, invstd, _, _ = oa.bn_fwd(B, x, H(kw["g"]), H(kw["b"]), 1e-5, 0.1, None, None, "conv")
+            ya = oops.store(oops.act_fwd(y, oops.ACT_RELU), spec.dtype)
+            v, idx = oa.maxpool_points_fwd(B, ya)
+            Nb, C = v.shape[0], v.shape[1] // B
+            t3 = lambda a: a.reshape(Nb, B, C).transpose(1, 0, 2)
+            check(H(kw["mean"]), mean, 1e-5, f"{lay} bn mean")
+            check(H(kw["invstd"]), invstd, 1e-5, f"{lay} bn invstd")
+            check(H(kw["v"]), t3(v), tol, f"{lay} pooled")
+            gi = H(kw["idx"])
+            mism = gi != t3(idx)            # only legitimate at a near-tie of the maximum
+            if mism.any():
+                at = np.take_along_axis(ya, gi.transpose(1, 0, 2).reshape(Nb, B * C, 1).astype(np.int64), axis=2)[:, :, 0]
+                assert np.all(t3(at)[mism] >= t3(v)[mism] - tol * (np.abs(t3(v)[mism]) + np.abs(ya).max()))
+            assert mism.mean() <= 0.02
+        elif op == "bn_bwd_maxpool":
+            x, g, b = H(kw["x"]), H(kw["g"]), H(kw["b"])
+            dv, idx = H(kw["dv"]), H(kw["idx"])
+            Bn, Nb, C = dv.shape
+            dyp = oa.maxpool_points_bwd(B, dv.transpose(1, 0, 2).reshape(Nb, B * C),
+                                        idx.transpose(1, 0, 2).reshape(Nb, B * C), x.shape[2])
+            y = oa.bn_fwd(B, x, g, b, 1e-5, 0.1, None, None, "conv")[0]
+            dy = oops.act_bwd(y, dyp, oops.ACT_RELU)
+            dx, dg, db = oa.bn_bwd(B, x, dy, g, H(kw["mean"]), H(kw["invstd"]), "conv")
+            kw2 = dict(kw); kw2["layout"] = "conv"
+            mg = np.abs(dg) / (dy.size / dg.size)
+            check(H(kw["dx"]), dx, tol, f"{lay} bn+pool dx", cancel(kw2, H(kw["mean"]), H(kw["invstd"]), mg))
+            for got, ref, nm in ((H(kw["dg"]), dg, "dgamma"), (H(kw["db"]), db, "dbeta")):
+                scale = max(np.abs(ref).max(), np.abs(dy).sum() / ref.size * 1e-3)
+                assert np.abs(got.reshape(-1) - ref).max() <= ftol * 10 * scale, f"{lay} bn+pool {nm}"
         elif op == "maxpool_points":
             v, idx = oa.maxpool_points_fwd(B, H(kw["x"]))
             Nb, C = v.shape[0], v.shape[1] // B
@@ -199,7 +230,8 @@ def test_c1_every_call_in_place(dtype):
     arr = FusedPointNetCls(spec, inp)
     seen = []
     arr.forward_backward(in_place_probe(spec, seen))
-    assert len(seen) == 5 * 2 + 1 + 3 + 2 + 1 + 1 + 1 + 2 + 3 + 1 + 5 * 2
+    # 5 conv + 4 bn + bn/pool | 3 linear + 2 bn + dropout + loss | dropout + 2 bn + 3 linear | bn/pool + 4 bn + 5 conv
+    assert len(seen) == (5 + 4 + 1) + (3 + 2 + 1 + 1) + (1 + 2 + 3) + (1 + 4 + 5)
     # forward results of the free-running chain stay close to the oracle's free-running chain
     states = [opn.init_state(inp["params"][b]) for b in range(spec.B)]
     outs = opn.array_train_step(spec, states, inp, 1)
