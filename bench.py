@@ -130,7 +130,7 @@ def time_steps(arr, torch, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
-def cpu_baseline(spec, budget_models=1, sample_nb=2):
+def cpu_baseline(spec, budget_models=1, sample_nb=16):
     """The oracle as it stands, on a bounded sample: `budget_models` model(s) and
     `sample_nb` clouds of the full point count; cost is linear in B*Nb."""
     import hfta_inputs as hi
@@ -159,6 +159,8 @@ def main():
     ap.add_argument("--workload", default="c1", choices=["c0", "c1"])
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (models are independent and would shard over "
@@ -174,6 +176,13 @@ def main():
         sys.exit(3)
     spec = hi.spec_c1() if args.workload == "c1" else hi.spec_c0()
     inp = hi.pointnet_cls_inputs(spec)
+
+    if args.copy_ref:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     tracer = Tracer(binding, torch)
     arrays.hb = tracer
@@ -198,8 +207,14 @@ def main():
                   for k, v in sorted(tot.items(), key=lambda kv: -kv[1][1])}
     dom, dv = max(tot.items(), key=lambda kv: kv[1][1])
     achieved = (dv[2] / dv[0]) / 1e9 / ((dv[1] / dv[0]) / 1e3)
+    # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    # runs of this same command (profiles/c1_pointnet_cls_hbm_traffic.md); null for other workloads
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "c1_pointnet_cls_traffic.json")
+    if args.workload == "c1" and os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(dom)
     roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=None,
+                    frac=achieved / HBM_PEAK_GBS, traffic=traffic,
                     avg_launch_us=1e3 * dv[1] / dv[0], launches_per_step=dv[0] // args.steps,
                     algorithmic_bytes_per_launch=dv[2] / dv[0],
                     share_of_step=(dv[1] / args.steps) / (sec * 1e3))

@@ -57,7 +57,7 @@ struct GemmArgs {
   int64_t c_ld, c_g0, c_g1;
   int64_t bias_g0, bias_g1;
   int M, N, K, S, G1;
-  int tiles_n, tiles_per_seg, total_tiles, splits;
+  int tiles_m, tiles_n, tiles_per_seg, total_tiles, splits;
   int a_vec, b_vec, c_vec, p_vec;
   int bias_mode, act;
   float slope;
@@ -315,9 +315,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs p) {
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  // XCD-aware placement: the hardware deals workgroups round-robin over the 8 XCDs (each with its
+  // own L2) in linear-id order.  Re-number so that every XCD walks one contiguous range of
+  // (batch, tile) work: the tiles of one batch item -- which share its operands -- meet in one
+  // L2, and inside a batch item the m-tiles that share a B tile run back to back.
+  int bx = blockIdx.x, bz = blockIdx.z;
+  {
+    const int total = gridDim.x * gridDim.z, per = total >> 3;
+    const int lin = blockIdx.x + gridDim.x * blockIdx.z;
+    if (lin < (per << 3)) {
+      const int l2 = (lin & 7) * per + (lin >> 3);
+      bz = l2 / gridDim.x;
+      bx = l2 - bz * gridDim.x;
+    }
+  }
+  const int tile_m = bx % p.tiles_m, tile_n = bx / p.tiles_m;
   const int m0 = tile_m * GEMM_BM, n0 = tile_n * GEMM_BN;
-  const int split = blockIdx.z % p.splits, g = blockIdx.z / p.splits;
+  const int split = bz % p.splits, g = bz / p.splits;
   const int g0 = g / p.G1, g1 = g % p.G1;
 
   const T* Ab = reinterpret_cast<const T*>(p.A) + g0 * p.a_g0 + g1 * p.a_g1;

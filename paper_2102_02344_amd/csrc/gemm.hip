@@ -70,6 +70,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   a.bias_g0 = d.bias_g0; a.bias_g1 = d.bias_g1;
   a.M = d.M; a.N = d.N; a.K = d.K; a.S = d.S; a.G1 = d.G1;
   a.tiles_n = (d.N + GEMM_BN - 1) / GEMM_BN;
+  a.tiles_m = (d.M + GEMM_BM - 1) / GEMM_BM;
   const int BK = d.dtype == HFTA_BF16 ? GemmT<bf16_raw>::BK : GemmT<float>::BK;
   a.tiles_per_seg = (d.K + BK - 1) / BK;
   a.total_tiles = d.S * a.tiles_per_seg;
