@@ -1,0 +1,219 @@
+"""Parity at the full sizes of the BASELINE configs, in the launch configuration the benchmark
+times.  A full oracle run is out of reach there (hundreds of GFLOP of float64), so:
+GEMM / convolution outputs are checked on seeded samples of output coordinates, each recomputed
+by the oracle's definition as an independent dot product from the very input bits the GPU read;
+reduction-type outputs (statistics, pooled maxima, parameter gradients of sampled channels,
+Adam) are checked in full for sampled channels / in full."""
+import numpy as np
+import pytest
+import torch
+
+import hfta_inputs as hi
+from oracle import ops as oops
+from util import DT, TOL
+
+pytestmark = pytest.mark.gpu
+bf = torch.bfloat16
+
+
+def f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def rel_ok(got, ref, tol, what):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    scale = np.sqrt(np.mean(ref * ref)) + 1e-30
+    bad = np.abs(got - ref) > tol * (np.abs(ref) + scale)
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} samples beyond tol, worst {np.abs(got - ref)[bad].max():.3e}"
+
+
+def test_c1_full_size_step_sampled():
+    """Config 1 as benchmarked: B=8, bf16, 32 clouds x 2500 points per model."""
+    from paper_2102_02344_amd.arrays import FusedPointNetCls
+    spec = hi.spec_c1()
+    inp = hi.pointnet_cls_inputs(spec)
+    arr = FusedPointNetCls(spec, inp)
+    B, Nb, L = spec.B, spec.Nb, spec.L
+    rng = np.random.default_rng(5)
+    tol = TOL["bf16"]
+    seen = []
+
+    def chan(t, b, C, c):          # [Nb, L] slice of channel (b, c) of a [Nb, B*C, L] tensor
+        return f64(t[:, b * C + c, :])
+
+    def probe(op, **kw):
+        lay = kw.get("layer", "")
+        if op == "conv1x1_fwd" and lay in ("conv0", "conv4"):
+            print("full-size check", op, lay, flush=True)
+            x, y = kw["x"], kw["y"]
+            Ci, Co = x.shape[1] // B, y.shape[1] // B
+            w = kw["w"].view(B, Co, Ci)
+            bias = kw["b"].view(B, Co)
+            S = 3000
+            n, b, o, l = (rng.integers(0, m, S) for m in (Nb, B, Co, L))
+            nt, bt, ot, lt = (torch.from_numpy(a).cuda() for a in (n, b, o, l))
+            ci = torch.arange(Ci, device="cuda")
+            xs = f64(x[nt[:, None], (bt * Ci)[:, None] + ci[None, :], lt[:, None]])          # [S, Ci]
+            ws = f64(w[bt, ot])                                                                 # [S, Ci]
+            ref = (xs * ws).sum(axis=1) + f64(bias[bt, ot])
+            rel_ok(f64(y[nt, bt * Co + ot, lt]), ref, tol, f"{lay} fwd")
+            seen.append(op + lay)
+        elif op == "bn_fwd_maxpool":
+            print("full-size check", op, flush=True)
+            C = kw["x"].shape[1] // B
+            for b, c in zip(rng.integers(0, B, 12), rng.integers(0, C, 12)):
+                z = chan(kw["x"], b, C, c)
+                k = b * C + c
+                g, bt_ = float(kw["g"][k]), float(kw["b"][k])
+                y, mean, invstd, _, _ = oops.bn_fwd(z[:, None, :], [g], [bt_], 1e-5)
+                assert abs(float(kw["mean"][k]) - mean[0]) <= 1e-5 * (abs(mean[0]) + np.sqrt(1 / invstd[0] ** 2))
+                assert abs(float(kw["invstd"][k]) - invstd[0]) <= 1e-5 * invstd[0]
+                ya = oops.store(oops.act_fwd(y[:, 0, :], oops.ACT_RELU), "bf16")
+                v, idx = oops.maxpool_points_fwd(ya[:, None, :])
+                gv, gi = f64(kw["v"][b, :, c]), kw["idx"][b, :, c].cpu().numpy()
+                rel_ok(gv, v[:, 0], tol, "pooled")
+                mism = gi != idx[:, 0]
+                if mism.any():      # legitimate only at a near-tie of the maximum
+                    at = ya[np.arange(Nb), gi]
+                    assert np.all(at[mism] >= v[mism, 0] - tol * (np.abs(v[mism, 0]) + np.abs(ya).max()))
+            seen.append(op)
+        elif op == "bn_bwd_maxpool":
+            print("full-size check", op, flush=True)
+            C = kw["x"].shape[1] // B
+            for b, c in zip(rng.integers(0, B, 8), rng.integers(0, C, 8)):
+                z = chan(kw["x"], b, C, c)
+                k = b * C + c
+                g, bt_ = float(kw["g"][k]), float(kw["b"][k])
+                mean, invstd = float(kw["mean"][k]), float(kw["invstd"][k])
+                dv, idx = f64(kw["dv"][b, :, c]), kw["idx"][b, :, c].cpu().numpy()
+                dy = oops.maxpool_points_bwd(dv[:, None], idx[:, None], L)[:, 0, :]
+                y = g * (z - mean) * invstd + bt_
+                gdy = oops.act_bwd(y, dy, oops.ACT_RELU)
+                dx, dg, dbt = oops.bn_bwd(z[:, None, :], gdy[:, None, :], [g], [mean], [invstd])
+                rel_ok(chan(kw["dx"], b, C, c), dx[:, 0, :], tol, "bn+pool dx")
+                sc = np.abs(dv).sum()
+                assert abs(float(kw["dg"][k]) - dg[0]) <= 2e-4 * max(abs(dg[0]), 1e-2 * sc)
+                assert abs(float(kw["db"][k]) - dbt[0]) <= 2e-4 * max(abs(dbt[0]), 1e-2 * sc)
+            seen.append(op)
+        elif op == "conv1x1_bwd" and lay == "conv4":
+            print("full-size check", op, lay, flush=True)
+            x, dy = kw["x"], kw["dy"]
+            Ci, Co = x.shape[1] // B, dy.shape[1] // B
+            dw = kw["dw"].view(B, Co, Ci)
+            w = kw["w"].view(B, Co, Ci)
+            for b, o, c in zip(rng.integers(0, B, 24), rng.integers(0, Co, 24), rng.integers(0, Ci, 24)):
+                ref = (chan(dy, b, Co, o) * chan(x, b, Ci, c)).sum()
+                terms = np.abs(chan(dy, b, Co, o) * chan(x, b, Ci, c)).sum()
+                assert abs(float(dw[b, o, c]) - ref) <= 2e-4 * max(abs(ref), 1e-2 * terms), "conv4 dW"
+            S = 2000
+            n, b, c, l = (rng.integers(0, m, S) for m in (Nb, B, Ci, L))
+            nt, bt, ct, lt = (torch.from_numpy(a).cuda() for a in (n, b, c, l))
+            co = torch.arange(Co, device="cuda")
+            dys = f64(dy[nt[:, None], (bt * Co)[:, None] + co[None, :], lt[:, None]])         # [S, Co]
+            ws = f64(w[bt, :, ct])                                                              # [S, Co]
+            rel_ok(f64(kw["dx"][nt, bt * Ci + ct, lt]), (dys * ws).sum(axis=1), tol, "conv4 dX")
+            seen.append(op + lay)
+
+    arr.forward_backward(probe)
+    torch.cuda.synchronize()
+    assert set(seen) == {"conv1x1_fwdconv0", "conv1x1_fwdconv4", "bn_fwd_maxpool", "bn_bwd_maxpool", "conv1x1_bwdconv4"}
+    assert np.all(np.isfinite(arr.loss.cpu().numpy()))
+    # Adam over the whole arena, in full, from the gradients the GPU just produced
+    th0, g = f64(arr.theta), f64(arr.grad)
+    arr.adam()
+    torch.cuda.synchronize()
+    th1 = f64(arr.theta)
+    for j, (name, shp) in enumerate(arr.shapes):
+        o, n = arr.seg_offsets[j], arr.seg_offsets[j + 1] - arr.seg_offsets[j]
+        sl = slice(B * o, B * (o + n))
+        for b in range(B):
+            sb = slice(B * o + b * n, B * o + (b + 1) * n)
+            ref, _, _ = oops.adam_step(th0[sb], g[sb], np.zeros(n), np.zeros(n), inp["lr"][b], inp["beta1"][b],
+                                       inp["beta2"][b], inp["eps"][b], inp["wd"][b], 1)
+            assert np.abs(th1[sb] - ref).max() <= 1e-5 * max(np.abs(ref).max(), 1e-30), name
+    assert torch.equal(arr.lowp, arr.theta.to(bf))
+
+
+@pytest.mark.parametrize("Fx,Fy", [(512, 2048), (2048, 512)])
+def test_c4_linear_full_size_sampled(Fx, Fy):
+    """Config 4's GEMMs: B=16 models, 32 x 128 = 4096 tokens per model, bf16."""
+    from paper_2102_02344_amd import binding as hb
+    B, M = 16, 4096
+    g = torch.Generator(device="cuda").manual_seed(40 + Fx)
+    X = torch.randn(B, M, Fx, device="cuda", generator=g).to(bf)
+    W = (torch.randn(B, Fx, Fy, device="cuda", generator=g) * (6.0 / Fx) ** 0.5).to(bf)
+    bias = torch.randn(B, Fy, device="cuda", generator=g).to(bf)
+    dY = torch.randn(B, M, Fy, device="cuda", generator=g).to(bf)
+    Y = torch.empty(B, M, Fy, device="cuda", dtype=bf)
+    dX = torch.empty_like(X)
+    dW = torch.empty(B, Fx, Fy, device="cuda")
+    db = torch.empty(B, Fy, device="cuda")
+    ws = torch.empty(max(4, hb.linear_bwd_workspace_bytes(B, M, Fx, Fy, DT["bf16"])), dtype=torch.uint8, device="cuda")
+    hb.linear_fwd(B, M, Fx, Fy, DT["bf16"], X, W, bias, Y, hb.ACT_GELU)
+    hb.linear_bwd(B, M, Fx, Fy, DT["bf16"], X, W, dY, dX, dW, db, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(7)
+    S = 4096
+    b, r, i, j = (torch.from_numpy(rng.integers(0, m, S)).cuda() for m in (B, M, Fx, Fy))
+    ref = (f64(X[b, r, :]) * f64(W[b, :, j])).sum(axis=1) + f64(bias[b, j])
+    rel_ok(f64(Y[b, r, j]), oops.act_fwd(ref, oops.ACT_GELU), TOL["bf16"], "Y = gelu(XW + b)")
+    rel_ok(f64(dX[b, r, i]), (f64(dY[b, r, :]) * f64(W[b, i, :])).sum(axis=1), TOL["bf16"], "dX")
+    rel_ok(f64(dW[b, i, j]), (f64(X[b, :, i]) * f64(dY[b, :, j])).sum(axis=1), 2e-4, "dW")
+    rel_ok(f64(db), f64(dY).sum(axis=1), 2e-4, "dbias")
+
+
+@pytest.mark.parametrize("Ci,Co,H", [(64, 128, 32), (3, 64, 64)])
+def test_c3_conv2d_full_size_sampled(Ci, Co, H):
+    """Config 3's discriminator layers: B=10 models, 64 images per model, 4x4 stride 2 pad 1, bf16."""
+    from paper_2102_02344_amd import binding as hb
+    B, Nb, k, s, p = 10, 64, 4, 2, 1
+    Ho = H // 2
+    g = torch.Generator(device="cuda").manual_seed(30 + Ci)
+    X = (torch.rand(Nb, B * Ci, H, H, device="cuda", generator=g) * 2 - 1).to(bf)
+    W = (torch.randn(B * Co, Ci, k, k, device="cuda", generator=g) * 0.02).to(bf)
+    dY = torch.randn(Nb, B * Co, Ho, Ho, device="cuda", generator=g).to(bf)
+    Y = torch.empty_like(dY)
+    dX = torch.empty_like(X)
+    dW = torch.empty(B * Co, Ci, k, k, device="cuda")
+    ws = torch.empty(max(4, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, H, k, k, s, p, DT["bf16"])),
+                     dtype=torch.uint8, device="cuda")
+    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, H, k, k, s, p, DT["bf16"], X, W, None, Y)
+    hb.conv2d_grouped_bwd(B, Nb, Ci, Co, H, H, k, k, s, p, DT["bf16"], X, W, dY, dX, dW, None, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    Xp = torch.nn.functional.pad(X, (p, p, p, p))              # zero padding only; no arithmetic
+    S = 1500
+    n, b, o, y, x = (torch.from_numpy(rng.integers(0, m, S)).cuda() for m in (Nb, B, Co, Ho, Ho))
+    # forward: window of the padded input against the filter
+    ci = torch.arange(Ci, device="cuda")
+    ky = torch.arange(k, device="cuda")
+    win = Xp[n[:, None, None, None], (b * Ci)[:, None, None, None] + ci[None, :, None, None],
+             (s * y)[:, None, None, None] + ky[None, None, :, None], (s * x)[:, None, None, None] + ky[None, None, None, :]]
+    ref = (f64(win) * f64(W[b * Co + o])).sum(axis=(1, 2, 3))
+    rel_ok(f64(Y[n, b * Co + o, y, x]), ref, TOL["bf16"], "Y")
+    # weight gradient of sampled filter taps: full reduction over (n, y, x)
+    for b_, o_, c_, ky_, kx_ in zip(*(rng.integers(0, m, 16) for m in (B, Co, Ci, k, k))):
+        xs = f64(Xp[:, b_ * Ci + c_, ky_:ky_ + s * Ho:s, kx_:kx_ + s * Ho:s])
+        d = f64(dY[:, b_ * Co + o_])
+        ref = (xs * d).sum()
+        assert abs(float(dW[b_ * Co + o_, c_, ky_, kx_]) - ref) <= 2e-4 * max(abs(ref), 1e-2 * np.abs(xs * d).sum())
+    # data gradient at sampled input pixels: sum over (o, ky, kx) with (iy + p - ky) divisible by s
+    S2 = 400
+    n, b, c, iy, ix = (rng.integers(0, m, S2) for m in (Nb, B, Ci, H, H))
+    dYh, Wh = f64(dY[:8]), f64(W)          # restrict to the first 8 images to bound the host copy
+    n = n % 8
+    got = f64(dX[:8])[n, b * Ci + c, iy, ix]
+    ref = np.zeros(S2)
+    for q in range(S2):
+        acc = 0.0
+        for ky_ in range(k):
+            ty = iy[q] + p - ky_
+            if ty % s or not (0 <= ty // s < Ho):
+                continue
+            for kx_ in range(k):
+                tx = ix[q] + p - kx_
+                if tx % s or not (0 <= tx // s < Ho):
+                    continue
+                acc += (dYh[n[q], b[q] * Co:(b[q] + 1) * Co, ty // s, tx // s] * Wh[b[q] * Co:(b[q] + 1) * Co, c[q], ky_, kx_]).sum()
+        ref[q] = acc
+    rel_ok(got, ref, TOL["bf16"], "dX")
