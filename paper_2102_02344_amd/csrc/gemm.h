@@ -227,6 +227,52 @@ __device__ __forceinline__ void mma_tile<float>(f32x16_t (&acc)[2][2], const uns
 constexpr int EPI_PITCH2 = 128 * 2 + 8;    // bytes, 2-byte outputs: 8-byte aligned rows
 constexpr int EPI_PITCH4 = 128 * 4 + 16;   // bytes, 4-byte outputs: 16-byte aligned rows
 
+// Phase 1 of the epilogue: accumulators (+ per-row bias, cheap activation) -> LDS staging tile in
+// the output type.  `pass` selects the 64-row half for 4-byte outputs (two passes), ignored for
+// 2-byte outputs (all 128 rows at once).  The caller owns the barriers around it.
+__device__ __forceinline__ float cheap_act(float x, int act, float slope) {
+  if (act == HFTA_ACT_RELU) return x > 0.f ? x : 0.f;
+  if (act == HFTA_ACT_LEAKY) return x > 0.f ? x : slope * x;
+  return x;
+}
+
+template <typename OutT, typename BiasT>
+__device__ __forceinline__ void stage_acc(f32x16_t (&acc)[2][2], unsigned char* lds, int pass, int M, int m0,
+                                          const BiasT* row_bias, int act, float slope, int t) {
+  constexpr int ES = sizeof(OutT);
+  constexpr int RP = ES == 2 ? 128 : 64;
+  constexpr int PITCH = ES == 2 ? EPI_PITCH2 : EPI_PITCH4;
+  const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+  const int ml = lane & 31, nq = (lane >> 5) * 4;
+  if (RP == 128 || wm == pass) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int rl = (RP == 128 ? wm * 64 : 0) + i * 32 + ml;
+      const int m = m0 + wm * 64 + i * 32 + ml;
+      float bm = 0.f;
+      if (row_bias && m < M) bm = Elem<BiasT>::load(row_bias + m);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int nl = wn * 64 + j * 32 + 8 * q + nq;
+          float x[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = cheap_act(acc[i][j][4 * q + e] + bm, act, slope);
+          unsigned char* dst = lds + rl * PITCH + nl * ES;
+          if (ES == 2) {
+            uint2 o;
+            o.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
+            o.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+            *reinterpret_cast<uint2*>(dst) = o;
+          } else {
+            *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+          }
+        }
+    }
+  }
+}
+
 template <typename OutT, typename BiasT>
 __device__ __forceinline__ void store_tile(f32x16_t (&acc)[2][2], unsigned char* lds, OutT* Cb, int64_t c_ld,
                                            int M, int N, int m0, int n0, const BiasT* bias, int bias_mode,
