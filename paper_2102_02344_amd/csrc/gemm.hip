@@ -13,6 +13,8 @@ __global__ void splitk_reduce_kernel(const float* __restrict__ partial, float* _
   out[i] = s;
 }
 
+int gemm_big_launch(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t st);
+
 static inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 static int total_tiles(const GemmDesc& d) {
@@ -102,6 +104,27 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   };
   a.c_vec = store_bytes(d.C, d.c_ld, d.c_g0, d.c_g1);
   a.p_vec = splits > 1 ? store_bytes(d.partial, d.N, (int64_t)d.M * d.N, 0) : 0;
+
+  // Compute-bound problems (MLP-sized bf16 GEMMs) take the 256x256 kernel: it needs the fast-path
+  // alignment (every 16/8-byte piece all-inside or all-outside), no split, and enough tiles to give
+  // every compute unit at least one.
+  if (d.dtype == HFTA_BF16 && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 128) {
+    auto piecewise = [&](int vec, bool kc, int extent_mn) {
+      if (vec == 0) return false;
+      if (kc) return d.K % (vec == 2 ? 8 : 4) == 0;
+      return extent_mn % 4 == 0;
+    };
+    const int64_t t256 = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * G;
+    if (piecewise(a.a_vec, d.a_kc, d.M) && piecewise(a.b_vec, d.b_kc, d.N) && t256 >= 192) {
+      GemmArgs b = a;
+      b.tiles_m = (d.M + 255) / 256;
+      b.tiles_n = (d.N + 255) / 256;
+      b.tiles_per_seg = (d.K + 63) / 64;
+      b.total_tiles = d.S * b.tiles_per_seg;
+      dim3 grid((unsigned)(b.tiles_m * b.tiles_n), 1, (unsigned)G);
+      return gemm_big_launch(d, b, grid, st);
+    }
+  }
 
   const int tiles_m = (d.M + GEMM_BM - 1) / GEMM_BM;
   dim3 grid((unsigned)(tiles_m * a.tiles_n), 1, (unsigned)(G * splits));

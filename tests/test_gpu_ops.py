@@ -31,7 +31,9 @@ def f32_tol(dtype):
 
 # ------------------------------------------------------------------ linear
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("B,M,Fx,Fy", [(3, 300, 200, 260), (2, 5, 1024, 16), (1, 129, 7, 3), (4, 32, 256, 512)])
+@pytest.mark.parametrize("B,M,Fx,Fy", [(3, 300, 200, 260), (2, 5, 1024, 16), (1, 129, 7, 3), (4, 32, 256, 512),
+                                        # many models, ragged 256x256 tiles: all three forms take the compute-bound kernel
+                                        (100, 320, 264, 200), (50, 260, 136, 300)])
 def test_linear_fwd_bwd(hb, dtype, B, M, Fx, Fy):
     print(f"linear {dtype} B={B} M={M} Fx={Fx} Fy={Fy}", flush=True)
     x = hi.normal(1, (B, M, Fx), dtype)
