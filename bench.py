@@ -151,6 +151,64 @@ def cpu_baseline(spec, budget_models=1, sample_nb=16):
                        f"({dt:.1f} s), numpy float64; host has {os.cpu_count()} logical cores")
 
 
+def ops_report(torch, binding):
+    """Operator-level rooflines at the shapes of the other BASELINE configs (not the headline
+    line): config 4's MLP GEMMs against the bf16 MFMA peak, config 3's grouped 4x4 stride-2
+    convolutions, each timed with HIP events on the launch stream."""
+    hb = binding
+    bf = torch.bfloat16
+    MFMA_PEAK = 2500.0          # TFLOP/s, dense bf16
+
+    def timeit(fn, n=20, warm=5):
+        for _ in range(warm):
+            fn()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(n):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / n * 1e-3
+
+    out = []
+    B, M = 16, 4096
+    for fx, fy in ((512, 2048), (2048, 512)):
+        X = torch.randn(B, M, fx, device="cuda").to(bf)
+        W = (torch.randn(B, fx, fy, device="cuda") / fx ** 0.5).to(bf)
+        bias = torch.randn(B, fy, device="cuda").to(bf)
+        Y = torch.empty(B, M, fy, device="cuda", dtype=bf)
+        dY = torch.randn(B, M, fy, device="cuda").to(bf)
+        dX = torch.empty_like(X)
+        dW = torch.empty(B, fx, fy, device="cuda")
+        ws = torch.empty(max(4, hb.linear_bwd_workspace_bytes(B, M, fx, fy, 1)), dtype=torch.uint8, device="cuda")
+        fl = 2.0 * B * M * fx * fy
+        for name, fn in (("linear_fwd+gelu", lambda: hb.linear_fwd(B, M, fx, fy, 1, X, W, bias, Y, hb.ACT_GELU)),
+                         ("linear_dX", lambda: hb.linear_bwd(B, M, fx, fy, 1, None, W, dY, dX, None, None, None)),
+                         ("linear_dW", lambda: hb.linear_bwd(B, M, fx, fy, 1, X, None, dY, None, dW, None, ws))):
+            t = timeit(fn)
+            out.append(dict(op=name, workload=f"c4 B=16 M=4096 {fx}->{fy} bf16", ms=t * 1e3, bound="mfma",
+                            achieved=fl / t / 1e12, peak=MFMA_PEAK, unit="TFLOP/s", frac=fl / t / 1e12 / MFMA_PEAK))
+    B, Nb = 10, 64
+    for ci, co, H in ((3, 64, 64), (64, 128, 32), (128, 256, 16), (256, 512, 8)):
+        Ho = H // 2
+        X = torch.randn(Nb, B * ci, H, H, device="cuda").to(bf)
+        W = (torch.randn(B * co, ci, 4, 4, device="cuda") * 0.02).to(bf)
+        Y = torch.empty(Nb, B * co, Ho, Ho, device="cuda", dtype=bf)
+        dY = torch.randn_like(Y)
+        dX = torch.empty_like(X)
+        dW = torch.empty(B * co, ci, 4, 4, device="cuda")
+        ws = torch.empty(max(4, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1)),
+                         dtype=torch.uint8, device="cuda")
+        fl = 2.0 * B * Nb * Ho * Ho * ci * co * 16
+        for name, fn in (("conv2d_fwd", lambda: hb.conv2d_grouped_fwd(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1, X, W, None, Y)),
+                         ("conv2d_dX", lambda: hb.conv2d_grouped_bwd(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1, None, W, dY, dX, None, None, None)),
+                         ("conv2d_dW", lambda: hb.conv2d_grouped_bwd(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1, X, None, dY, None, dW, None, ws))):
+            t = timeit(fn)
+            out.append(dict(op=name, workload=f"c3 B=10 Nb=64 {ci}->{co} {H}x{H} k4 s2 p1 bf16", ms=t * 1e3, bound="mfma",
+                            achieved=fl / t / 1e12, peak=MFMA_PEAK, unit="TFLOP/s", frac=fl / t / 1e12 / MFMA_PEAK))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +217,8 @@ def main():
     ap.add_argument("--workload", default="c1", choices=["c0", "c1"])
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--ops-report", default=None,
+                    help="also time the GEMM / conv2d entry points at config 4 / config 3 shapes and write JSON here")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -255,6 +315,9 @@ def main():
                    "conv": list(spec.conv), "fc": list(spec.fc), "step": "fwd+bwd+Adam"},
         "roofline": roofline, "serial_b1": serial, "cpu_baseline": cpu, "kernels": per_kernel,
     }
+    if args.ops_report:
+        with open(args.ops_report, "w") as f:
+            json.dump(ops_report(torch, binding), f, indent=1)
     print(json.dumps(out))
 
 
