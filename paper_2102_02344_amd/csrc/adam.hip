@@ -70,8 +70,8 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamArgs p) {
     *reinterpret_cast<float4*>(p.v + base + i) = v;
     if (p.lowp) {
       uint2 o;
-      o.x = (uint32_t)f32_to_bf16(th.x) | ((uint32_t)f32_to_bf16(th.y) << 16);
-      o.y = (uint32_t)f32_to_bf16(th.z) | ((uint32_t)f32_to_bf16(th.w) << 16);
+      o.x = pack_bf16x2(th.x, th.y);
+      o.y = pack_bf16x2(th.z, th.w);
       *reinterpret_cast<uint2*>(p.lowp + base + i) = o;
     }
   } else {
@@ -139,8 +139,8 @@ __global__ __launch_bounds__(256) void adam_multi_kernel(AdamMultiArgs p) {
     *reinterpret_cast<float4*>(p.v + i) = v;
     if (p.lowp) {
       uint2 o;
-      o.x = (uint32_t)f32_to_bf16(th.x) | ((uint32_t)f32_to_bf16(th.y) << 16);
-      o.y = (uint32_t)f32_to_bf16(th.z) | ((uint32_t)f32_to_bf16(th.w) << 16);
+      o.x = pack_bf16x2(th.x, th.y);
+      o.y = pack_bf16x2(th.z, th.w);
       *reinterpret_cast<uint2*>(p.lowp + i) = o;
     }
   } else {

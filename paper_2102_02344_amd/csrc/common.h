@@ -11,12 +11,18 @@ typedef uint16_t bf16_raw;  // bf16 bit pattern; storage only
 __device__ __forceinline__ float bf16_to_f32(bf16_raw h) {
   return __uint_as_float(((uint32_t)h) << 16);
 }
-// round to nearest even; NaN stays NaN
+// round to nearest even (the matrix-core generation's own conversion instruction)
 __device__ __forceinline__ bf16_raw f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_raw)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_raw)(u >> 16);
+  const __bf16 b = (__bf16)f;
+  return *reinterpret_cast<const bf16_raw*>(&b);
+}
+// two floats -> two bf16 in one 32-bit word (lo in the low half): one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+  return *reinterpret_cast<const uint32_t*>(&b);
 }
 
 template <typename T> struct Elem;

@@ -22,6 +22,7 @@
 // k-tile).
 #pragma once
 #include "common.h"
+#include <type_traits>
 
 namespace hfta {
 
@@ -61,6 +62,7 @@ struct GemmArgs {
   int a_vec, b_vec, c_vec, p_vec;
   int bias_mode, act;
   float slope;
+  uint32_t a_extent, b_extent;   // bytes from an operand slice's first to one past its last element
 };
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -227,18 +229,32 @@ __device__ __forceinline__ void mma_tile<float>(f32x16_t (&acc)[2][2], const uns
 constexpr int EPI_PITCH2 = 128 * 2 + 8;    // bytes, 2-byte outputs: 8-byte aligned rows
 constexpr int EPI_PITCH4 = 128 * 4 + 16;   // bytes, 4-byte outputs: 16-byte aligned rows
 
-// Phase 1 of the epilogue: accumulators (+ per-row bias, cheap activation) -> LDS staging tile in
-// the output type.  `pass` selects the 64-row half for 4-byte outputs (two passes), ignored for
-// 2-byte outputs (all 128 rows at once).  The caller owns the barriers around it.
 __device__ __forceinline__ float cheap_act(float x, int act, float slope) {
   if (act == HFTA_ACT_RELU) return x > 0.f ? x : 0.f;
   if (act == HFTA_ACT_LEAKY) return x > 0.f ? x : slope * x;
   return x;
 }
 
-template <typename OutT, typename BiasT>
-__device__ __forceinline__ void stage_acc(f32x16_t (&acc)[2][2], unsigned char* lds, int pass, int M, int m0,
-                                          const BiasT* row_bias, int act, float slope, int t) {
+// Activation kinds the staging code is specialised for: the three select-only ones are resolved
+// at compile time (a run-time switch costs a scalar branch per element, and the epilogue's vector
+// ALU work is what bounds the memory-bound shapes); ACT_ANY evaluates the run-time `act`.
+enum { EPI_NONE = 0, EPI_RELU = 1, EPI_LEAKY = 2, EPI_ANY = 3 };
+
+template <int KIND>
+__device__ __forceinline__ float epi_act(float x, int act, float slope) {
+  if (KIND == EPI_NONE) return x;
+  if (KIND == EPI_RELU) return fmaxf(x, 0.f);
+  if (KIND == EPI_LEAKY) return x > 0.f ? x : slope * x;
+  return apply_act(x, act, slope);
+}
+
+// Phase 1 of the epilogue: accumulators (+ bias, activation) -> LDS staging tile in the output
+// type.  `pass` selects the 64-row half for 4-byte outputs (two passes), ignored for 2-byte
+// outputs (all 128 rows at once).  COLB: the bias is per column n (else per row m).  The caller
+// owns the barriers around it.
+template <typename OutT, typename BiasT, int KIND, bool COLB>
+__device__ __forceinline__ void stage_pass(f32x16_t (&acc)[2][2], unsigned char* lds, int pass, int M, int N,
+                                           int m0, int n0, const BiasT* bias, int act, float slope, int t) {
   constexpr int ES = sizeof(OutT);
   constexpr int RP = ES == 2 ? 128 : 64;
   constexpr int PITCH = ES == 2 ? EPI_PITCH2 : EPI_PITCH4;
@@ -250,7 +266,7 @@ __device__ __forceinline__ void stage_acc(f32x16_t (&acc)[2][2], unsigned char* 
       const int rl = (RP == 128 ? wm * 64 : 0) + i * 32 + ml;
       const int m = m0 + wm * 64 + i * 32 + ml;
       float bm = 0.f;
-      if (row_bias && m < M) bm = Elem<BiasT>::load(row_bias + m);
+      if (!COLB && bias && m < M) bm = Elem<BiasT>::load(bias + m);
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -258,12 +274,16 @@ __device__ __forceinline__ void stage_acc(f32x16_t (&acc)[2][2], unsigned char* 
           const int nl = wn * 64 + j * 32 + 8 * q + nq;
           float x[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) x[e] = cheap_act(acc[i][j][4 * q + e] + bm, act, slope);
+          for (int e = 0; e < 4; ++e) {
+            x[e] = acc[i][j][4 * q + e] + bm;
+            if (COLB && n0 + nl + e < N) x[e] += Elem<BiasT>::load(bias + n0 + nl + e);
+            x[e] = epi_act<KIND>(x[e], act, slope);
+          }
           unsigned char* dst = lds + rl * PITCH + nl * ES;
           if (ES == 2) {
             uint2 o;
-            o.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
-            o.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+            o.x = pack_bf16x2(x[0], x[1]);
+            o.y = pack_bf16x2(x[2], x[3]);
             *reinterpret_cast<uint2*>(dst) = o;
           } else {
             *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
@@ -273,81 +293,88 @@ __device__ __forceinline__ void stage_acc(f32x16_t (&acc)[2][2], unsigned char* 
   }
 }
 
+// Row-bias / no-bias staging with one of the select-only activations (used directly by kernels
+// that interleave their own work between staging and stores).
 template <typename OutT, typename BiasT>
+__device__ __forceinline__ void stage_acc(f32x16_t (&acc)[2][2], unsigned char* lds, int pass, int M, int m0,
+                                          const BiasT* row_bias, int act, float slope, int t) {
+  if (act == HFTA_ACT_RELU) stage_pass<OutT, BiasT, EPI_RELU, false>(acc, lds, pass, M, 0, m0, 0, row_bias, act, slope, t);
+  else if (act == HFTA_ACT_LEAKY) stage_pass<OutT, BiasT, EPI_LEAKY, false>(acc, lds, pass, M, 0, m0, 0, row_bias, act, slope, t);
+  else stage_pass<OutT, BiasT, EPI_NONE, false>(acc, lds, pass, M, 0, m0, 0, row_bias, act, slope, t);
+}
+
+// Phase 2: staged rows -> global memory.  VB = bytes per lane (16, 8: whole aligned pieces of a
+// row, consecutive lanes on consecutive pieces so a wavefront's store covers whole row segments;
+// 0: single elements).  INTERIOR: the tile lies wholly inside the matrix, no per-lane checks.
+template <typename OutT, int VB, bool INTERIOR>
+__device__ __forceinline__ void store_rows(const unsigned char* lds, OutT* Cb, int64_t c_ld, int M, int N,
+                                           int mbase, int n0, int t) {
+  constexpr int ES = sizeof(OutT);
+  constexpr int RP = ES == 2 ? 128 : 64;
+  constexpr int PITCH = ES == 2 ? EPI_PITCH2 : EPI_PITCH4;
+  if constexpr (VB > 0) {
+    constexpr int EPV = VB / ES;                         // elements per piece
+    constexpr int PPR = 128 / EPV;                       // pieces per row
+    constexpr int RPI = GEMM_THREADS / PPR;              // rows per iteration
+    const int r0 = t / PPR, c = t % PPR;
+    const unsigned char* src = lds + r0 * PITCH + c * VB;
+    OutT* dst = Cb + (int64_t)(mbase + r0) * c_ld + n0 + c * EPV;
+    const int n = n0 + c * EPV;
+#pragma unroll 4
+    for (int it = 0; it < RP / RPI; ++it) {
+      const int m = mbase + r0 + it * RPI;
+      typedef typename std::conditional<VB == 16, uint4, uint2>::type V;
+      const V v = *reinterpret_cast<const V*>(src + it * RPI * PITCH);
+      OutT* d = dst + (int64_t)it * RPI * c_ld;
+      if (INTERIOR || (m < M && n + EPV <= N)) {
+        *reinterpret_cast<V*>(d) = v;
+      } else if (m < M && n < N) {
+        const OutT* e = reinterpret_cast<const OutT*>(&v);
+#pragma unroll
+        for (int k = 0; k < EPV; ++k)
+          if (n + k < N) d[k] = e[k];
+      }
+    }
+  } else {
+#pragma unroll 2
+    for (int it = 0; it < RP * 128 / GEMM_THREADS; ++it) {
+      const int id = t + GEMM_THREADS * it;
+      const int r = id / 128, c = id % 128;
+      const int m = mbase + r, n = n0 + c;
+      if (m < M && n < N) Cb[(int64_t)m * c_ld + n] = *reinterpret_cast<const OutT*>(lds + r * PITCH + c * ES);
+    }
+  }
+}
+
+// The whole epilogue of a 128x128 tile.  ALLOW_FULL = false leaves out the per-column-bias and
+// transcendental-activation code for kernels whose host side never asks for them.
+template <typename OutT, typename BiasT, bool ALLOW_FULL = true>
 __device__ __forceinline__ void store_tile(f32x16_t (&acc)[2][2], unsigned char* lds, OutT* Cb, int64_t c_ld,
                                            int M, int N, int m0, int n0, const BiasT* bias, int bias_mode,
                                            int act, float slope, int c_vec, int t) {
-  constexpr int ES = sizeof(OutT);
-  constexpr int RP = ES == 2 ? 128 : 64;                 // rows per pass
-  constexpr int PITCH = ES == 2 ? EPI_PITCH2 : EPI_PITCH4;
-  constexpr int EPC = 16 / ES;                           // elements per 16-byte chunk
-  constexpr int CPR = 128 / EPC;                         // chunks per row
-  const int lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-  const int ml = lane & 31, nq = (lane >> 5) * 4;
+  constexpr int RP = sizeof(OutT) == 2 ? 128 : 64;       // rows per pass
+  const bool colb = bias && bias_mode == 2;
+  const bool full = ALLOW_FULL && (colb || act == HFTA_ACT_TANH || act == HFTA_ACT_GELU);
+  const BiasT* rb = bias_mode == 1 ? bias : nullptr;
+  const bool interior = m0 + 128 <= M && n0 + 128 <= N;
 #pragma unroll
   for (int pass = 0; pass < 128 / RP; ++pass) {
-    if (RP == 128 || wm == pass) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int rl = (RP == 128 ? wm * 64 : 0) + i * 32 + ml;
-        const int m = m0 + wm * 64 + i * 32 + ml;
-        float bm = 0.f;
-        if (bias && bias_mode == 1 && m < M) bm = Elem<BiasT>::load(bias + m);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int nl = wn * 64 + j * 32 + 8 * q + nq;
-            float x[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              x[e] = acc[i][j][4 * q + e] + bm;
-              if (bias && bias_mode == 2 && n0 + nl + e < N) x[e] += Elem<BiasT>::load(bias + n0 + nl + e);
-              x[e] = apply_act(x[e], act, slope);
-            }
-            unsigned char* dst = lds + rl * PITCH + nl * ES;
-            if (ES == 2) {
-              uint2 o;
-              o.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
-              o.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
-              *reinterpret_cast<uint2*>(dst) = o;
-            } else {
-              *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
-            }
-          }
-      }
+    if (full) {
+      if (colb) stage_pass<OutT, BiasT, EPI_ANY, true>(acc, lds, pass, M, N, m0, n0, bias, act, slope, t);
+      else stage_pass<OutT, BiasT, EPI_ANY, false>(acc, lds, pass, M, N, m0, n0, rb, act, slope, t);
+    } else {
+      stage_acc<OutT, BiasT>(acc, lds, pass, M, m0, rb, act, slope, t);
     }
     __syncthreads();
-#pragma unroll
-    for (int it = 0; it < RP * CPR / GEMM_THREADS; ++it) {
-      const int id = t + GEMM_THREADS * it;
-      const int r = id / CPR, c = id % CPR;
-      const int m = m0 + pass * RP + r;
-      const int n = n0 + c * EPC;
-      if (m >= M || n >= N) continue;
-      const unsigned char* src = lds + r * PITCH + c * 16;
-      uint2 lo = *reinterpret_cast<const uint2*>(src);
-      uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
-      OutT* dst = Cb + (int64_t)m * c_ld + n;
-      if (c_vec == 16 && n + EPC <= N) {
-        *reinterpret_cast<uint4*>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      } else if (c_vec >= 8 && n + EPC <= N) {
-        *reinterpret_cast<uint2*>(dst) = lo;
-        *reinterpret_cast<uint2*>(dst + EPC / 2) = hi;
-      } else if (c_vec >= 8 && n + EPC / 2 <= N) {
-        *reinterpret_cast<uint2*>(dst) = lo;
-        const OutT* e = reinterpret_cast<const OutT*>(&hi);
-#pragma unroll
-        for (int k = 0; k < EPC / 2; ++k)
-          if (n + EPC / 2 + k < N) dst[EPC / 2 + k] = e[k];
-      } else {
-        OutT e[EPC];
-        *reinterpret_cast<uint2*>(e) = lo;
-        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(e) + 8) = hi;
-#pragma unroll
-        for (int k = 0; k < EPC; ++k)
-          if (n + k < N) dst[k] = e[k];
-      }
+    const int mbase = m0 + pass * RP;
+    if (c_vec == 16) {
+      if (interior) store_rows<OutT, 16, true>(lds, Cb, c_ld, M, N, mbase, n0, t);
+      else store_rows<OutT, 16, false>(lds, Cb, c_ld, M, N, mbase, n0, t);
+    } else if (c_vec == 8) {
+      if (interior) store_rows<OutT, 8, true>(lds, Cb, c_ld, M, N, mbase, n0, t);
+      else store_rows<OutT, 8, false>(lds, Cb, c_ld, M, N, mbase, n0, t);
+    } else {
+      store_rows<OutT, 0, false>(lds, Cb, c_ld, M, N, mbase, n0, t);
     }
     if (pass + 1 < 128 / RP) __syncthreads();
   }
@@ -424,12 +451,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs p) {
 
   if (p.splits > 1) {
     float* Pb = p.partial + ((int64_t)split * (gridDim.z / p.splits) + g) * (int64_t)p.M * p.N;
-    store_tile<float, T>(acc, &smem[0][0][0], Pb, p.N, p.M, p.N, m0, n0, nullptr, 0, HFTA_ACT_NONE, 0.f, p.p_vec, t);
+    store_tile<float, T, false>(acc, &smem[0][0][0], Pb, p.N, p.M, p.N, m0, n0, nullptr, 0, HFTA_ACT_NONE, 0.f, p.p_vec, t);
     return;
   }
   OutT* Cb = reinterpret_cast<OutT*>(p.C) + g0 * p.c_g0 + g1 * p.c_g1;
   const T* bias = p.bias ? reinterpret_cast<const T*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
-  store_tile<OutT, T>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t);
+  // bf16 operands with an fp32 result (weight gradients) never carry a column bias or a
+  // transcendental activation (checked by the host)
+  store_tile<OutT, T, sizeof(T) == sizeof(OutT)>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t);
 }
 
 int gemm_pick_splits(const GemmDesc& d);

@@ -1,5 +1,6 @@
 // Host side of the batched GEMM core: split selection, alignment checks, dispatch.
 #include "gemm.h"
+#include "gemm_pf.h"
 
 namespace hfta {
 
@@ -63,6 +64,9 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   const int splits = d.splits < 1 ? 1 : d.splits;
   if (G * splits > 65535) return HFTA_EUNSUPPORTED;
   if (splits > 1 && (!d.partial || !d.out_f32 || d.bias || d.act != HFTA_ACT_NONE)) return HFTA_EINVAL;
+  if (d.dtype == HFTA_BF16 && d.out_f32 &&
+      ((d.bias && d.bias_mode == 2) || d.act == HFTA_ACT_TANH || d.act == HFTA_ACT_GELU))
+    return HFTA_EUNSUPPORTED;
 
   GemmArgs a;
   a.A = d.A; a.Bm = d.Bm; a.C = d.C; a.bias = d.bias; a.partial = d.partial;
@@ -79,6 +83,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   a.splits = splits;
   a.bias_mode = d.bias ? d.bias_mode : 0;
   a.act = d.act; a.slope = d.slope;
+  a.a_extent = a.b_extent = 0;
 
   // vector-load eligibility: every address the fast path forms must be aligned
   const int es = (int)dtype_size(d.dtype);
@@ -108,7 +113,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   // Compute-bound problems (MLP-sized bf16 GEMMs) take the 256x256 kernel: it needs the fast-path
   // alignment (every 16/8-byte piece all-inside or all-outside), no split, and enough tiles to give
   // every compute unit at least one.
-  if (d.dtype == HFTA_BF16 && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 128) {
+  if (d.dtype == HFTA_BF16 && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 512) {
     auto piecewise = [&](int vec, bool kc, int extent_mn) {
       if (vec == 0) return false;
       if (kc) return d.K % (vec == 2 ? 8 : 4) == 0;
@@ -128,7 +133,27 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
 
   const int tiles_m = (d.M + GEMM_BM - 1) / GEMM_BM;
   dim3 grid((unsigned)(tiles_m * a.tiles_n), 1, (unsigned)(G * splits));
-  int rc = d.dtype == HFTA_BF16 ? launch_layout<bf16_raw>(d, a, grid, st) : launch_layout<float>(d, a, grid, st);
+  int rc;
+  // bf16 problems whose operands can be fetched in whole 8/16-byte pieces take the deep-prefetch
+  // kernel (branch-free buffer loads, several k-tiles in flight).
+  const int64_t a_ext = ((d.a_kc ? (int64_t)(d.M - 1) * d.a_ld + d.K : (int64_t)(d.K - 1) * d.a_ld + d.M)) * es;
+  const int64_t b_ext = ((d.b_kc ? (int64_t)(d.N - 1) * d.b_ld + d.K : (int64_t)(d.K - 1) * d.b_ld + d.N)) * es;
+  auto whole_pieces = [&](int vec, bool kc, int extent_mn, bool v16) {
+    if (vec == 0 || (v16 && kc && vec != 2)) return false;
+    if (kc) return d.K % (v16 ? 8 : 4) == 0;
+    return extent_mn % 4 == 0;
+  };
+  bool pf = d.dtype == HFTA_BF16 && a_ext < (int64_t)1 << 31 && b_ext < (int64_t)1 << 31 &&
+            d.a_ld > 0 && d.b_ld > 0 && (d.a_kc || !d.b_kc);
+  bool v16 = pf && (d.a_kc || d.b_kc) && whole_pieces(a.a_vec, d.a_kc, d.M, true) && whole_pieces(a.b_vec, d.b_kc, d.N, true);
+  pf = pf && (v16 || (whole_pieces(a.a_vec, d.a_kc, d.M, false) && whole_pieces(a.b_vec, d.b_kc, d.N, false)));
+  if (pf) {
+    a.a_extent = (uint32_t)a_ext;
+    a.b_extent = (uint32_t)b_ext;
+    rc = gemm_pf_launch(d, a, v16, grid, st);
+  } else {
+    rc = d.dtype == HFTA_BF16 ? launch_layout<bf16_raw>(d, a, grid, st) : launch_layout<float>(d, a, grid, st);
+  }
   if (rc != HFTA_OK) return rc;
   if (splits > 1) {
     const int64_t count = G * (int64_t)d.M * d.N;

@@ -201,8 +201,8 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
           unsigned char* dst = smem + rl * PITCH + nl * ES;
           if (ES == 2) {
             uint2 o;
-            o.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
-            o.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+            o.x = pack_bf16x2(x[0], x[1]);
+            o.y = pack_bf16x2(x[2], x[3]);
             *reinterpret_cast<uint2*>(dst) = o;
           } else {
             *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);

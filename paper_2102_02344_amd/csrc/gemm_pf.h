@@ -1,0 +1,184 @@
+// Deep-prefetch variant of the 128x128 bf16 GEMM kernel.
+//
+// Same tiling, LDS layout, MFMA schedule and epilogue as gemm_kernel; what differs is how operand
+// tiles travel from memory to LDS.  PF k-tiles are in flight in registers at any time instead of
+// one, which is what a workgroup needs to keep HBM busy when the k-loop does little arithmetic per
+// byte (the fused k=1 convolutions of a point-cloud model: K = 64..1024 against millions of
+// columns).  For the hardware to overlap them, the loads of a step must not sit under control
+// flow: every load is a raw buffer load whose offset is either inside the operand slice or a
+// fixed out-of-range value, for which the hardware returns zeros and makes no memory request.
+// Rows / columns beyond the matrix, k beyond K and k-tiles beyond the end of the loop are all
+// expressed that way, so the steady-state loop issues PF-1 tiles ahead with no branches.
+//
+// Eligibility (checked by the host): bf16 operands, every 8-byte (16-byte when V16) piece of an
+// operand either wholly inside or wholly outside the matrix, each operand slice below 2 GiB.
+#pragma once
+#include "gemm.h"
+
+namespace hfta {
+
+typedef uint32_t pf_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t pf_u32x2 __attribute__((ext_vector_type(2)));
+constexpr uint32_t PF_OOB = 0x80000000u;   // >= any slice extent: the load returns zeros
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t pf_rsrc(const void* p, uint32_t bytes) {
+  // raw buffer (stride 0), 32-bit data format; the range check is offset >= bytes
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// Per-thread addressing of one operand; q-sets (the staged data) are kept apart so that several
+// tiles can be in flight with one copy of the offsets.
+template <bool KC, bool V16> struct PfOperand;
+
+template <bool V16> struct PfOperand<true, V16> {   // k-contiguous: rows t/4 and t/4+64, 16-byte group t%4
+  typedef uint4 Regs[2];
+  uint32_t off[2];
+  int kg;
+  __device__ __forceinline__ void init(int row0, int rows, int64_t ld, int t) {
+    kg = (t & 3) * 8;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int r = row0 + (t >> 2) + 64 * h;
+      off[h] = r < rows ? (uint32_t)((int64_t)r * ld * 2) + (uint32_t)kg * 2u : PF_OOB;
+    }
+  }
+  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K, bool live) const {
+    const int k = k0 + kg;
+    if (V16) {
+      const bool ok = live && k + 8 <= K;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(ok ? off[h] + (uint32_t)k0 * 2u : PF_OOB), 0, 0);
+        q[h] = make_uint4(v.x, v.y, v.z, v.w);
+      }
+    } else {
+      const bool ok0 = live && k + 4 <= K, ok1 = live && k + 8 <= K;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint32_t o = off[h] + (uint32_t)k0 * 2u;
+        const pf_u32x2 lo = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok0 ? o : PF_OOB), 0, 0);
+        const pf_u32x2 hi = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok1 ? o + 8u : PF_OOB), 0, 0);
+        q[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
+    }
+  }
+  static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) { store_kc(tile, q, t); }
+};
+
+template <bool V16> struct PfOperand<false, V16> {  // m/n-contiguous: 4(k) x 4(n) block, k-quad t%8, n-group t/8
+  typedef uint2 Regs[4];
+  uint32_t off[4];
+  uint32_t ldb;
+  int kq4;
+  __device__ __forceinline__ void init(int col0, int cols, int64_t ld, int t) {
+    kq4 = 4 * (t % 8);
+    ldb = (uint32_t)(ld * 2);
+    const int c = col0 + (t / 8) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      off[j] = c + 4 <= cols ? (uint32_t)(kq4 + j) * ldb + (uint32_t)c * 2u : PF_OOB;
+  }
+  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K, bool live) const {
+    const uint32_t kb = (uint32_t)k0 * ldb;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool ok = live && k0 + kq4 + j < K;
+      const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok ? off[j] + kb : PF_OOB), 0, 0);
+      q[j] = make_uint2(v.x, v.y);
+    }
+  }
+  static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) { store_nc_bf16(tile, q, t); }
+};
+
+template <bool A_KC, bool B_KC, typename OutT, bool V16, int PF>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_pf_kernel(GemmArgs p) {
+  typedef bf16_raw T;
+  constexpr int BK = GemmT<T>::BK;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][GEMM_TILE_BYTES];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int bx = blockIdx.x, bz = blockIdx.z;
+  {  // XCD-aware renumbering, as in gemm_kernel
+    const int total = gridDim.x * gridDim.z, per = total >> 3;
+    const int lin = blockIdx.x + gridDim.x * blockIdx.z;
+    if (lin < (per << 3)) {
+      const int l2 = (lin & 7) * per + (lin >> 3);
+      bz = l2 / gridDim.x;
+      bx = l2 - bz * gridDim.x;
+    }
+  }
+  const int tile_m = bx % p.tiles_m, tile_n = bx / p.tiles_m;
+  const int m0 = tile_m * GEMM_BM, n0 = tile_n * GEMM_BN;
+  const int split = bz % p.splits, g = bz / p.splits;
+  const int g0 = g / p.G1, g1 = g % p.G1;
+
+  const T* Ab = reinterpret_cast<const T*>(p.A) + g0 * p.a_g0 + g1 * p.a_g1;
+  const T* Bb = reinterpret_cast<const T*>(p.Bm) + g0 * p.b_g0 + g1 * p.b_g1;
+
+  const int t_begin = (int)((int64_t)p.total_tiles * split / p.splits);
+  const int t_end = (int)((int64_t)p.total_tiles * (split + 1) / p.splits);
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  PfOperand<A_KC, V16> oa;
+  PfOperand<B_KC, V16> ob;
+  oa.init(m0, p.M, p.a_ld, t);
+  ob.init(n0, p.N, p.b_ld, t);
+  typename PfOperand<A_KC, V16>::Regs ra[PF];
+  typename PfOperand<B_KC, V16>::Regs rb[PF];
+
+  auto issue = [&](int set, int tt) {
+    const bool live = tt < t_end;
+    const int tc = live ? tt : t_begin;
+    const int seg = tc / p.tiles_per_seg;
+    const int k0 = (tc - seg * p.tiles_per_seg) * BK;
+    oa.load(ra[set], pf_rsrc(Ab + seg * p.a_ss, p.a_extent), k0, p.K, live);
+    ob.load(rb[set], pf_rsrc(Bb + seg * p.b_ss, p.b_extent), k0, p.K, live);
+  };
+
+  if (t_begin < t_end) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) issue(d, t_begin + d);
+    oa.store(smem[0][0], ra[0], t);
+    ob.store(smem[0][1], rb[0], t);
+    __syncthreads();
+    int buf = 0;
+    bool done = false;
+    for (int base = t_begin; !done; base += PF) {
+#pragma unroll
+      for (int d = 0; d < PF; ++d) {
+        const int cur = base + d;          // tile in LDS buffer `buf`; it came through register set d
+        issue(d, cur + PF);                // set d is free again; beyond the end: zeros, no traffic
+        mma_tile<T>(acc, smem[buf][0], smem[buf][1], wm, wn, lane);
+        if (cur + 1 >= t_end) { done = true; break; }
+        oa.store(smem[buf ^ 1][0], ra[(d + 1) % PF], t);
+        ob.store(smem[buf ^ 1][1], rb[(d + 1) % PF], t);
+        __syncthreads();
+        buf ^= 1;
+      }
+    }
+    __syncthreads();
+  }
+
+  if (p.splits > 1) {
+    float* Pb = p.partial + ((int64_t)split * (gridDim.z / p.splits) + g) * (int64_t)p.M * p.N;
+    store_tile<float, T, false>(acc, &smem[0][0][0], Pb, p.N, p.M, p.N, m0, n0, nullptr, 0, HFTA_ACT_NONE, 0.f, p.p_vec, t);
+    return;
+  }
+  OutT* Cb = reinterpret_cast<OutT*>(p.C) + g0 * p.c_g0 + g1 * p.c_g1;
+  const T* bias = p.bias ? reinterpret_cast<const T*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
+  // fp32 results of bf16 operands are weight gradients: the host never pairs them with a column bias
+  // or a transcendental activation, and leaving that code out halves the kernel's registers
+  store_tile<OutT, T, sizeof(OutT) == 2>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t);
+}
+
+int gemm_pf_launch(const GemmDesc& d, const GemmArgs& a, bool v16, dim3 grid, hipStream_t st);
+
+}  // namespace hfta

@@ -3,6 +3,11 @@
 // plus the bias-gradient reductions.
 #include "gemm.h"
 
+namespace hfta {
+int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
+                       const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st);
+}
+
 using namespace hfta;
 
 namespace {
@@ -157,6 +162,10 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
   if (rc != HFTA_OK) return rc;
   if (!X || !W || !Y || !xs || !ys || !valid_act(act)) return HFTA_EINVAL;
   if (xs[3] != 1 || ys[3] != 1) return HFTA_EUNSUPPORTED;
+  if (dtype == HFTA_BF16) {   // wide layer, few input channels: streaming kernel
+    rc = hfta::conv1x1_stream_fwd(B, Nb, Ci, Co, L, X, xs, W, bias, Y, ys, act, act_slope, as_stream(stream));
+    if (rc != HFTA_EUNSUPPORTED) return rc;
+  }
   GemmDesc d = base_desc(dtype);
   d.A = W; d.Bm = X; d.C = Y;
   d.M = Co; d.N = L; d.K = Ci; d.G0 = B; d.G1 = Nb;
