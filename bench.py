@@ -78,8 +78,13 @@ def kernel_label(name, a):
     if name in ("bn_fwd", "bn_bwd"):
         lay = "linear" if a[3] == 1 else "conv"
         return f"{name}_{lay}_kernel"
-    if name in ("conv1x1_fwd", "linear_fwd"):
-        return "gemm_kernel(fwd)"
+    if name == "conv1x1_fwd":
+        B, Nb, Ci, Co, L, dt = a[:6]
+        if dt == 1 and Ci <= 128 and Ci % 8 == 0 and Co >= 256 and L % 4 == 0:
+            return "conv1x1_stream_kernel"
+        return "gemm_pf_kernel(fwd)" if dt == 1 else "gemm_kernel(fwd)"
+    if name == "linear_fwd":
+        return "gemm_pf_kernel(fwd)" if a[4] == 1 else "gemm_kernel(fwd)"
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
     return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",

@@ -110,24 +110,38 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   a.c_vec = store_bytes(d.C, d.c_ld, d.c_g0, d.c_g1);
   a.p_vec = splits > 1 ? store_bytes(d.partial, d.N, (int64_t)d.M * d.N, 0) : 0;
 
-  // Compute-bound problems (MLP-sized bf16 GEMMs) take the 256x256 kernel: it needs the fast-path
-  // alignment (every 16/8-byte piece all-inside or all-outside), no split, and enough tiles to give
-  // every compute unit at least one.
-  if (d.dtype == HFTA_BF16 && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 512) {
-    auto piecewise = [&](int vec, bool kc, int extent_mn) {
-      if (vec == 0) return false;
-      if (kc) return d.K % (vec == 2 ? 8 : 4) == 0;
-      return extent_mn % 4 == 0;
-    };
+  // operand slice extents for the buffer-load kernels
+  const int64_t a_ext = ((d.a_kc ? (int64_t)(d.M - 1) * d.a_ld + d.K : (int64_t)(d.K - 1) * d.a_ld + d.M)) * es;
+  const int64_t b_ext = ((d.b_kc ? (int64_t)(d.N - 1) * d.b_ld + d.K : (int64_t)(d.K - 1) * d.b_ld + d.N)) * es;
+  const bool buffers_ok = d.dtype == HFTA_BF16 && a_ext < (int64_t)1 << 31 && b_ext < (int64_t)1 << 31 &&
+                          d.a_ld > 0 && d.b_ld > 0 && (d.a_kc || !d.b_kc);
+  auto whole_pieces = [&](int vec, bool kc, int extent_mn, bool v16) {
+    if (vec == 0 || (v16 && kc && vec != 2)) return false;
+    if (kc) return d.K % (v16 ? 8 : 4) == 0;
+    return extent_mn % 4 == 0;
+  };
+  const bool v16 = buffers_ok && (d.a_kc || d.b_kc) && whole_pieces(a.a_vec, d.a_kc, d.M, true) &&
+                   whole_pieces(a.b_vec, d.b_kc, d.N, true);
+  const bool v8 = buffers_ok && whole_pieces(a.a_vec, d.a_kc, d.M, false) && whole_pieces(a.b_vec, d.b_kc, d.N, false);
+  if (buffers_ok) {
+    a.a_extent = (uint32_t)a_ext;
+    a.b_extent = (uint32_t)b_ext;
+  }
+
+  // Compute-bound problems (MLP-sized bf16 GEMMs) take the 256x256 kernel: it needs 16-byte
+  // loadable operands, no split, a long reduction, and enough tiles to give every compute unit
+  // at least one.
+  if ((v16 || (v8 && !d.a_kc && !d.b_kc)) && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 512) {
     const int64_t t256 = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * G;
-    if (piecewise(a.a_vec, d.a_kc, d.M) && piecewise(a.b_vec, d.b_kc, d.N) && t256 >= 192) {
+    if (t256 >= 192) {
       GemmArgs b = a;
       b.tiles_m = (d.M + 255) / 256;
       b.tiles_n = (d.N + 255) / 256;
       b.tiles_per_seg = (d.K + 63) / 64;
       b.total_tiles = d.S * b.tiles_per_seg;
       dim3 grid((unsigned)(b.tiles_m * b.tiles_n), 1, (unsigned)G);
-      return gemm_big_launch(d, b, grid, st);
+      const int rc = gemm_big_launch(d, b, grid, st);
+      if (rc != HFTA_EUNSUPPORTED) return rc;
     }
   }
 
@@ -136,20 +150,8 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   int rc;
   // bf16 problems whose operands can be fetched in whole 8/16-byte pieces take the deep-prefetch
   // kernel (branch-free buffer loads, several k-tiles in flight).
-  const int64_t a_ext = ((d.a_kc ? (int64_t)(d.M - 1) * d.a_ld + d.K : (int64_t)(d.K - 1) * d.a_ld + d.M)) * es;
-  const int64_t b_ext = ((d.b_kc ? (int64_t)(d.N - 1) * d.b_ld + d.K : (int64_t)(d.K - 1) * d.b_ld + d.N)) * es;
-  auto whole_pieces = [&](int vec, bool kc, int extent_mn, bool v16) {
-    if (vec == 0 || (v16 && kc && vec != 2)) return false;
-    if (kc) return d.K % (v16 ? 8 : 4) == 0;
-    return extent_mn % 4 == 0;
-  };
-  bool pf = d.dtype == HFTA_BF16 && a_ext < (int64_t)1 << 31 && b_ext < (int64_t)1 << 31 &&
-            d.a_ld > 0 && d.b_ld > 0 && (d.a_kc || !d.b_kc);
-  bool v16 = pf && (d.a_kc || d.b_kc) && whole_pieces(a.a_vec, d.a_kc, d.M, true) && whole_pieces(a.b_vec, d.b_kc, d.N, true);
-  pf = pf && (v16 || (whole_pieces(a.a_vec, d.a_kc, d.M, false) && whole_pieces(a.b_vec, d.b_kc, d.N, false)));
+  const bool pf = v16 || v8;
   if (pf) {
-    a.a_extent = (uint32_t)a_ext;
-    a.b_extent = (uint32_t)b_ext;
     rc = gemm_pf_launch(d, a, v16, grid, st);
   } else {
     rc = d.dtype == HFTA_BF16 ? launch_layout<bf16_raw>(d, a, grid, st) : launch_layout<float>(d, a, grid, st);

@@ -2,14 +2,19 @@
 //
 // The 128x128 kernel in gemm.h reads 32 bytes of LDS per MFMA cycle and wave, which is the
 // whole LDS bandwidth of a compute unit, and moves 64 flop per byte it pulls from L2.  For the
-// MLP-sized GEMMs (M, N >= 256, K >= 128) this kernel doubles both ratios: eight wavefronts in a
+// MLP-sized GEMMs (M, N >= 256, K >= 512) this kernel doubles both ratios: eight wavefronts in a
 // 2 (m) x 4 (n) grid each own a 128x64 block (4 x 2 MFMA 32x32x16 blocks, 128 fp32
 // accumulators), k-tiles are 64 elements (128 bytes per row) staged in LDS as
-// [row][128 B + 16 B pad], double-buffered, with the next k-tile's global loads parked in
-// registers while the current one is multiplied.  One workgroup per compute unit (147 KB LDS).
-// bf16 storage only; operands must satisfy the fast-path alignment rules of the 128x128 kernel.
+// [row][128 B + 16 B pad], double-buffered.  Two k-tiles are in flight in registers behind the
+// one being multiplied; their loads are branch-free raw buffer loads (out-of-range offset =
+// zeros, no memory request; see gemm_pf.h), so the hardware overlaps them with the MFMAs.
+// One workgroup per compute unit (147 KB LDS).  bf16 storage only.
+//
+// The epilogue is specialised at compile time (EPI_*): with one workgroup per compute unit
+// nothing overlaps it, and a run-time switch per element or an exact erf costs as much as the
+// k-loop of a K = 512 problem.
 #pragma once
-#include "gemm.h"
+#include "gemm_pf.h"
 
 namespace hfta {
 
@@ -20,59 +25,103 @@ constexpr int BIG_TILE = 256 * BIG_PITCH;                // 36864 bytes per oper
 constexpr int BIG_SMEM = 4 * BIG_TILE;                   // two operands, two stages
 constexpr int BIG_EPI_PITCH = 256 * 2 + 8;               // bf16 staging row (8-byte aligned)
 constexpr int BIG_EPI_PITCH4 = 256 * 4 + 16;             // fp32 staging row
+constexpr int BIG_PF = 2;                                // k-tiles in flight in registers
 
-// k-contiguous operand: 256 rows x 8 chunks of 16 bytes, 4 chunks per thread
-struct BigStageKc {
-  uint4 q[4];
-  __device__ __forceinline__ void load(const bf16_raw* base, int64_t ld, int row0, int rows, int k0, int K, int vec, int t) {
+// Epilogue kinds.  SEL: y = max(x, 0) + neg_slope * min(x, 0) -- identity (1), ReLU (0) and
+// LeakyReLU (slope) without a branch.  GELU here is x * Phi(x) with erf from the Abramowitz-Stegun
+// 7.1.26 rational form (|error| < 1.5e-7, far below bf16 resolution), TANH the library's.
+enum { BIG_SEL = 0, BIG_TANH = 1, BIG_GELU = 2 };
+
+__device__ __forceinline__ float gelu_as(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float tt = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.f));
+  float poly = fmaf(tt, 1.061405429f, -1.453152027f);
+  poly = fmaf(tt, poly, 1.421413741f);
+  poly = fmaf(tt, poly, -0.284496736f);
+  poly = fmaf(tt, poly, 0.254829592f);
+  poly *= tt;
+  const float e = __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);
+  const float erf_abs = fmaf(-poly, e, 1.f);
+  const float erf_x = copysignf(erf_abs, x);
+  return 0.5f * x * (1.f + erf_x);
+}
+
+template <int ACT>
+__device__ __forceinline__ float big_act(float x, float neg_slope) {
+  if (ACT == BIG_SEL) return fmaf(neg_slope, fminf(x, 0.f), fmaxf(x, 0.f));
+  if (ACT == BIG_TANH) return tanhf(x);
+  return gelu_as(x);
+}
+
+// k-contiguous operand: 256 rows x 8 chunks of 16 bytes per k-tile, 4 chunks per thread
+template <bool V16> struct BigOpKc {
+  typedef uint4 Regs[4];
+  uint32_t off[4];
+  int kg;
+  __device__ __forceinline__ void init(int row0, int rows, int64_t ld, int t) {
+    kg = (t & 7) * 8;
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-      const int id = t + BIG_THREADS * h;
-      const int g = id & 7, r = row0 + (id >> 3);
-      const int k = k0 + g * 8;
-      const bf16_raw* src = base + (int64_t)r * ld + k;
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (vec == 2) {
-        if (r < rows && k + 8 <= K) v = *reinterpret_cast<const uint4*>(src);
-      } else {
-        if (r < rows && k + 4 <= K) { const uint2 lo = *reinterpret_cast<const uint2*>(src); v.x = lo.x; v.y = lo.y; }
-        if (r < rows && k + 8 <= K) { const uint2 hi = *reinterpret_cast<const uint2*>(src + 4); v.z = hi.x; v.w = hi.y; }
-      }
-      q[h] = v;
+      const int r = row0 + (t >> 3) + 64 * h;
+      off[h] = r < rows ? (uint32_t)((int64_t)r * ld * 2) + (uint32_t)kg * 2u : PF_OOB;
     }
   }
-  __device__ __forceinline__ void store(unsigned char* tile, int t) const {
+  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K) const {
+    const int k = k0 + kg;
+    if (V16) {
+      const bool ok = k + 8 <= K;
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const int id = t + BIG_THREADS * h;
-      *reinterpret_cast<uint4*>(tile + (id >> 3) * BIG_PITCH + (id & 7) * 16) = q[h];
+      for (int h = 0; h < 4; ++h) {
+        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(ok ? off[h] + (uint32_t)k0 * 2u : PF_OOB), 0, 0);
+        q[h] = make_uint4(v.x, v.y, v.z, v.w);
+      }
+    } else {
+      const bool ok0 = k + 4 <= K, ok1 = k + 8 <= K;
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        const uint32_t o = off[h] + (uint32_t)k0 * 2u;
+        const pf_u32x2 lo = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok0 ? o : PF_OOB), 0, 0);
+        const pf_u32x2 hi = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok1 ? o + 8u : PF_OOB), 0, 0);
+        q[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
     }
+  }
+  static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+      *reinterpret_cast<uint4*>(tile + ((t >> 3) + 64 * h) * BIG_PITCH + (t & 7) * 16) = q[h];
   }
 };
 
-// m/n-contiguous operand: [64 k][256 n] as 16 k-quads x 64 n-groups of 4(k) x 4(n) blocks, 2 per thread
-struct BigStageNc {
-  uint2 q[2][4];
-  __device__ __forceinline__ void load(const bf16_raw* base, int64_t ld, int col0, int cols, int k0, int K, int vec, int t) {
+// m/n-contiguous operand: [64 k][256 n] as 16 k-quads x 64 n-groups of 4(k) x 4(n) blocks; a
+// thread owns k-quads t%8 and t%8 + 8 of n-group t/8, transposed in registers on the way to LDS
+struct BigOpNc {
+  typedef uint2 Regs[2][4];
+  uint32_t off0;      // (4 * (t%8)) * ld * 2 + c * 2, or out of range when the columns are
+  uint32_t ldb;
+  int kq4;
+  __device__ __forceinline__ void init(int col0, int cols, int64_t ld, int t) {
+    kq4 = 4 * (t & 7);
+    ldb = (uint32_t)(ld * 2);
+    const int c = col0 + (t >> 3) * 4;
+    off0 = c + 4 <= cols ? (uint32_t)kq4 * ldb + (uint32_t)c * 2u : PF_OOB;
+  }
+  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K) const {
+    const uint32_t kb = (uint32_t)k0 * ldb;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int id = t + BIG_THREADS * h;
-      const int kq = (id >> 9) * 8 + (id & 7), ng = (id >> 3) & 63;
-      const int c = col0 + ng * 4;
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int k = k0 + 4 * kq + j;
-        uint2 v = make_uint2(0u, 0u);
-        if (k < K && c + 4 <= cols) v = *reinterpret_cast<const uint2*>(base + (int64_t)k * ld + c);
-        q[h][j] = v;
+        const bool ok = k0 + 32 * h + kq4 + j < K;
+        const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok ? off0 + kb + (uint32_t)(32 * h + j) * ldb : PF_OOB), 0, 0);
+        q[h][j] = make_uint2(v.x, v.y);
       }
-    }
   }
-  __device__ __forceinline__ void store(unsigned char* tile, int t) const {
+  static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) {
+    const int ng = t >> 3;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int id = t + BIG_THREADS * h;
-      const int kq = (id >> 9) * 8 + (id & 7), ng = (id >> 3) & 63;
+      const int kq = h * 8 + (t & 7);
       const uint32_t a0 = q[h][0].x, a1 = q[h][1].x, a2 = q[h][2].x, a3 = q[h][3].x;
       const uint32_t b0 = q[h][0].y, b1 = q[h][1].y, b2 = q[h][2].y, b3 = q[h][3].y;
       uint2 o[4];
@@ -87,13 +136,12 @@ struct BigStageNc {
   }
 };
 
-template <bool KC> struct BigStage;
-template <> struct BigStage<true> : BigStageKc {};
-template <> struct BigStage<false> : BigStageNc {};
+template <bool KC, bool V16> struct BigOp;
+template <bool V16> struct BigOp<true, V16> : BigOpKc<V16> {};
+template <bool V16> struct BigOp<false, V16> : BigOpNc {};
 
-// SLOW = true: per-column bias and/or tanh / GELU.  The fp32 accumulators are staged and bias +
-// activation run once per element in the rolled store loop (see store_tile_impl in gemm.h).
-template <bool A_KC, bool B_KC, typename OutT, bool SLOW>
+// COLB: bias per column n (the fused Linear's), else per row m or none.
+template <bool A_KC, bool B_KC, typename OutT, bool V16, bool COLB, int ACT>
 __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[BIG_SMEM];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -123,136 +171,160 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  BigStage<A_KC> sa;
-  BigStage<B_KC> sb;
-  auto issue = [&](int tt) {
-    const int seg = tt / p.tiles_per_seg;
-    const int k0 = (tt - seg * p.tiles_per_seg) * BIG_BK;
-    sa.load(Ab + seg * p.a_ss, p.a_ld, m0, p.M, k0, p.K, p.a_vec, t);
-    sb.load(Bb + seg * p.b_ss, p.b_ld, n0, p.N, k0, p.K, p.b_vec, t);
+  BigOp<A_KC, V16> oa;
+  BigOp<B_KC, V16> ob;
+  oa.init(m0, p.M, p.a_ld, t);
+  ob.init(n0, p.N, p.b_ld, t);
+  typename BigOp<A_KC, V16>::Regs ra[BIG_PF];
+  typename BigOp<B_KC, V16>::Regs rb[BIG_PF];
+  const int t_end = p.total_tiles;
+  auto issue = [&](int set, int tt) {
+    const bool live = tt < t_end;
+    const int Ke = live ? p.K : 0;      // a dead tile has no valid k: every offset out of range
+    const int tc = live ? tt : 0;
+    const int seg = tc / p.tiles_per_seg;
+    const int k0 = (tc - seg * p.tiles_per_seg) * BIG_BK;
+    oa.load(ra[set], pf_rsrc(Ab + seg * p.a_ss, p.a_extent), k0, Ke);
+    ob.load(rb[set], pf_rsrc(Bb + seg * p.b_ss, p.b_extent), k0, Ke);
   };
   auto tileA = [&](int buf) { return smem + buf * 2 * BIG_TILE; };
   auto tileB = [&](int buf) { return smem + buf * 2 * BIG_TILE + BIG_TILE; };
 
-  issue(0);
-  sa.store(tileA(0), t);
-  sb.store(tileB(0), t);
+#pragma unroll
+  for (int d = 0; d < BIG_PF; ++d) issue(d, d);
+  oa.store(tileA(0), ra[0], t);
+  ob.store(tileB(0), rb[0], t);
   __syncthreads();
   int buf = 0;
   const int r = lane & 31, gsel = lane >> 5;
-  for (int tt = 0; tt < p.total_tiles; ++tt) {
-    const bool more = tt + 1 < p.total_tiles;
-    if (more) issue(tt + 1);
-    const unsigned char* As = tileA(buf) + (wm * 128 + r) * BIG_PITCH + gsel * 16;
-    const unsigned char* Bs = tileB(buf) + (wn * 64 + r) * BIG_PITCH + gsel * 16;
+  bool done = false;
+  for (int base = 0; !done; base += BIG_PF) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8_t a[4], b[2];
+    for (int d = 0; d < BIG_PF; ++d) {
+      const int cur = base + d;
+      issue(d, cur + BIG_PF);
+      const unsigned char* As = tileA(buf) + (wm * 128 + r) * BIG_PITCH + gsel * 16;
+      const unsigned char* Bs = tileB(buf) + (wn * 64 + r) * BIG_PITCH + gsel * 16;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(As + i * 32 * BIG_PITCH + s * 32);
+      for (int s = 0; s < 4; ++s) {
+        bf16x8_t a[4], b[2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(Bs + j * 32 * BIG_PITCH + s * 32);
+        for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(As + i * 32 * BIG_PITCH + s * 32);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(Bs + j * 32 * BIG_PITCH + s * 32);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+      }
+      if (cur + 1 >= t_end) { done = true; break; }
+      oa.store(tileA(buf ^ 1), ra[(d + 1) % BIG_PF], t);
+      ob.store(tileB(buf ^ 1), rb[(d + 1) % BIG_PF], t);
+      __syncthreads();
+      buf ^= 1;
     }
-    if (more) {
-      sa.store(tileA(buf ^ 1), t);
-      sb.store(tileB(buf ^ 1), t);
-    }
-    __syncthreads();
-    buf ^= 1;
   }
+  __syncthreads();
 
-  // epilogue: stage through LDS in passes of 128 rows (2-byte staging) / 64 rows (4-byte staging),
-  // then wide row stores.  lane l holds row m = l % 32 and columns 8*(v/4) + 4*(l/32) + v%4 of
-  // each 32x32 block.
-  constexpr int ES = SLOW ? 4 : (int)sizeof(OutT);       // staged element size
-  constexpr int OS = sizeof(OutT);
+  // epilogue: bias + activation in registers, staged through LDS in the output type in passes of
+  // 128 rows (2-byte outputs) / 64 rows (4-byte outputs), then 16- or 8-byte row-major stores.
+  // lane l holds row m = l % 32 and columns 8*(v/4) + 4*(l/32) + v%4 of each 32x32 block.
+  constexpr int ES = sizeof(OutT);
   constexpr int RP = ES == 2 ? 128 : 64;
   constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
-  constexpr int EPC = 16 / ES, CPR = 256 / EPC;
   OutT* Cb = reinterpret_cast<OutT*>(p.C) + g0 * p.c_g0 + g1 * p.c_g1;
   const bf16_raw* bias = p.bias ? reinterpret_cast<const bf16_raw*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
   const int ml = lane & 31, nq = (lane >> 5) * 4;
-#pragma unroll 1
+  const float neg_slope = p.slope;
+
+  float cb[2][4][4];                                     // this lane's 32 column biases
+  if (COLB) {
+    const __amdgpu_buffer_rsrc_t rbias = pf_rsrc(bias, (uint32_t)p.N * 2u);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * 64 + j * 32 + 8 * q + nq;
+        const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rbias, (int)(n + 4 <= p.N ? (uint32_t)n * 2u : PF_OOB), 0, 0);
+        cb[j][q][0] = __uint_as_float(v.x << 16);
+        cb[j][q][1] = __uint_as_float(v.x & 0xffff0000u);
+        cb[j][q][2] = __uint_as_float(v.y << 16);
+        cb[j][q][3] = __uint_as_float(v.y & 0xffff0000u);
+      }
+  }
+
+#pragma unroll
   for (int pass = 0; pass < 256 / RP; ++pass) {
+    if (wm == pass * RP / 128) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = wm * 128 + i * 32;                 // first row of this block inside the tile
-      if (row / RP != pass) continue;
-      const int rl = row % RP + ml;
-      const int m = m0 + row + ml;
-      float bm = 0.f;
-      if (bias && p.bias_mode == 1 && m < p.M) bm = bf16_to_f32(bias[m]);
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 32;                          // first row of this block inside the wave's 128
+        if (row / RP != (pass * RP % 128) / RP) continue;
+        const int rl = row % RP + ml;
+        const int m = m0 + wm * 128 + row + ml;
+        float bm = 0.f;
+        if (!COLB && bias && m < p.M) bm = bf16_to_f32(bias[m]);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int nl = wn * 64 + j * 32 + 8 * q + nq;
-          float x[4];
+          for (int q = 0; q < 4; ++q) {
+            const int nl = wn * 64 + j * 32 + 8 * q + nq;
+            float x[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            x[e] = acc[i][j][4 * q + e] + bm;
-            if (!SLOW) x[e] = cheap_act(x[e], p.act, p.slope);
+            for (int e = 0; e < 4; ++e)
+              x[e] = big_act<ACT>(acc[i][j][4 * q + e] + (COLB ? cb[j][q][e] : bm), neg_slope);
+            unsigned char* dst = smem + rl * PITCH + nl * ES;
+            if (ES == 2) {
+              uint2 o;
+              o.x = pack_bf16x2(x[0], x[1]);
+              o.y = pack_bf16x2(x[2], x[3]);
+              *reinterpret_cast<uint2*>(dst) = o;
+            } else {
+              *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+            }
           }
-          unsigned char* dst = smem + rl * PITCH + nl * ES;
-          if (ES == 2) {
-            uint2 o;
-            o.x = pack_bf16x2(x[0], x[1]);
-            o.y = pack_bf16x2(x[2], x[3]);
-            *reinterpret_cast<uint2*>(dst) = o;
-          } else {
-            *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
-          }
-        }
+      }
     }
     __syncthreads();
-#pragma unroll 1
-    for (int id = t; id < RP * CPR; id += BIG_THREADS) {
-      const int rr = id / CPR, c = id % CPR;
-      const int m = m0 + pass * RP + rr, n = n0 + c * EPC;
-      if (m >= p.M || n >= p.N) continue;
-      const unsigned char* src = smem + rr * PITCH + c * 16;
-      OutT* dst = Cb + (int64_t)m * p.c_ld + n;
-      if (SLOW) {
-        const float4 v = *reinterpret_cast<const float4*>(src);
-        float x[4] = {v.x, v.y, v.z, v.w};
-        OutT o[4];
+    // RP rows x 256 columns out: consecutive lanes on consecutive pieces of a row
+    const int mbase = m0 + pass * RP;
+    if (p.c_vec == 16) {
+      constexpr int EPV = 16 / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
+      const int r0 = t / PPR, c = t % PPR, n = n0 + c * EPV;
+#pragma unroll 4
+      for (int it = 0; it < RP / RPI; ++it) {
+        const int rr = r0 + it * RPI, m = mbase + rr;
+        const uint4 v = *reinterpret_cast<const uint4*>(smem + rr * PITCH + c * 16);
+        OutT* dst = Cb + (int64_t)m * p.c_ld + n;
+        if (m < p.M && n + EPV <= p.N) {
+          *reinterpret_cast<uint4*>(dst) = v;
+        } else if (m < p.M && n < p.N) {
+          const OutT* e = reinterpret_cast<const OutT*>(&v);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (bias && p.bias_mode == 2 && n + e < p.N) x[e] += bf16_to_f32(bias[n + e]);
-          o[e] = Elem<OutT>::from_f32(apply_act(x[e], p.act, p.slope));
+          for (int k = 0; k < EPV; ++k)
+            if (n + k < p.N) dst[k] = e[k];
         }
-        if (n + 4 <= p.N && p.c_vec >= 4 * OS) {
-          if (OS == 2) *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o);
-          else *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(o);
-        } else {
+      }
+    } else {
+      constexpr int EPV = 8 / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
+      const int r0 = t / PPR, c = t % PPR, n = n0 + c * EPV;
+#pragma unroll 4
+      for (int it = 0; it < RP / RPI; ++it) {
+        const int rr = r0 + it * RPI, m = mbase + rr;
+        const uint2 v = *reinterpret_cast<const uint2*>(smem + rr * PITCH + c * 8);
+        OutT* dst = Cb + (int64_t)m * p.c_ld + n;
+        if (m < p.M && n + EPV <= p.N && p.c_vec == 8) {
+          *reinterpret_cast<uint2*>(dst) = v;
+        } else if (m < p.M && n < p.N) {
+          const OutT* e = reinterpret_cast<const OutT*>(&v);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n + e < p.N) dst[e] = o[e];
-        }
-      } else {
-        const uint2 lo = *reinterpret_cast<const uint2*>(src);
-        const uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
-        if (p.c_vec == 16 && n + EPC <= p.N) {
-          *reinterpret_cast<uint4*>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        } else if (p.c_vec >= 8 && n + EPC <= p.N) {
-          *reinterpret_cast<uint2*>(dst) = lo;
-          *reinterpret_cast<uint2*>(dst + EPC / 2) = hi;
-        } else {
-          OutT e[EPC];
-          *reinterpret_cast<uint2*>(e) = lo;
-          *reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(e) + 8) = hi;
-#pragma unroll
-          for (int k = 0; k < EPC; ++k)
+          for (int k = 0; k < EPV; ++k)
             if (n + k < p.N) dst[k] = e[k];
         }
       }
     }
-    __syncthreads();
+    if (pass + 1 < 256 / RP) __syncthreads();
   }
 }
 

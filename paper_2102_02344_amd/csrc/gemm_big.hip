@@ -3,24 +3,44 @@
 
 namespace hfta {
 
-template <bool A_KC, bool B_KC>
-static void launch_big(const GemmDesc& d, const GemmArgs& a, bool slow, dim3 grid, hipStream_t st) {
-  if (d.out_f32) {
-    if (slow) hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, float, true>), grid, dim3(BIG_THREADS), 0, st, a);
-    else hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, float, false>), grid, dim3(BIG_THREADS), 0, st, a);
-  } else {
-    if (slow) hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, bf16_raw, true>), grid, dim3(BIG_THREADS), 0, st, a);
-    else hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, bf16_raw, false>), grid, dim3(BIG_THREADS), 0, st, a);
-  }
+template <bool A_KC, bool B_KC, typename OutT, bool COLB, int ACT>
+static void launch_big(const GemmArgs& a, dim3 grid, hipStream_t st) {
+  hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, OutT, true, COLB, ACT>), grid, dim3(BIG_THREADS), 0, st, a);
 }
 
-// `a` must carry tile counts for 256x256 tiles and 64-element k-tiles.
-int gemm_big_launch(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t st) {
-  const bool slow = d.act == HFTA_ACT_TANH || d.act == HFTA_ACT_GELU || (d.bias && d.bias_mode == 2);
-  if (d.a_kc && !d.b_kc) launch_big<true, false>(d, a, slow, grid, st);
-  else if (d.a_kc && d.b_kc) launch_big<true, true>(d, a, slow, grid, st);
-  else if (!d.a_kc && !d.b_kc) launch_big<false, false>(d, a, slow, grid, st);
-  else return HFTA_EUNSUPPORTED;
+// `a` must carry tile counts for 256x256 tiles and 64-element k-tiles, operand extents, and 16-byte
+// loadable k-contiguous operands.  HFTA_EUNSUPPORTED: not a combination this kernel is built for.
+int gemm_big_launch(const GemmDesc& d, const GemmArgs& a0, dim3 grid, hipStream_t st) {
+  GemmArgs a = a0;
+  const bool colb = d.bias && d.bias_mode == 2;
+  const bool sel = d.act == HFTA_ACT_NONE || d.act == HFTA_ACT_RELU || d.act == HFTA_ACT_LEAKY;
+  a.slope = d.act == HFTA_ACT_NONE ? 1.f : d.act == HFTA_ACT_RELU ? 0.f : d.slope;
+  if (colb && (reinterpret_cast<uintptr_t>(d.bias) % 8 != 0 || d.bias_g0 % 4 != 0 || d.bias_g1 % 4 != 0 || d.N % 4 != 0))
+    return HFTA_EUNSUPPORTED;
+  if (d.out_f32) {
+    if (colb || !sel) return HFTA_EUNSUPPORTED;
+    if (d.a_kc && !d.b_kc) launch_big<true, false, float, false, BIG_SEL>(a, grid, st);
+    else if (d.a_kc && d.b_kc) launch_big<true, true, float, false, BIG_SEL>(a, grid, st);
+    else if (!d.a_kc && !d.b_kc) launch_big<false, false, float, false, BIG_SEL>(a, grid, st);
+    else return HFTA_EUNSUPPORTED;
+    return launch_status();
+  }
+  if (d.a_kc && !d.b_kc) {
+    if (colb) {
+      if (sel) launch_big<true, false, bf16_raw, true, BIG_SEL>(a, grid, st);
+      else if (d.act == HFTA_ACT_GELU) launch_big<true, false, bf16_raw, true, BIG_GELU>(a, grid, st);
+      else launch_big<true, false, bf16_raw, true, BIG_TANH>(a, grid, st);
+    } else {
+      if (sel) launch_big<true, false, bf16_raw, false, BIG_SEL>(a, grid, st);
+      else if (d.act == HFTA_ACT_GELU) launch_big<true, false, bf16_raw, false, BIG_GELU>(a, grid, st);
+      else launch_big<true, false, bf16_raw, false, BIG_TANH>(a, grid, st);
+    }
+  } else {
+    if (colb || !sel) return HFTA_EUNSUPPORTED;
+    if (d.a_kc && d.b_kc) launch_big<true, true, bf16_raw, false, BIG_SEL>(a, grid, st);
+    else if (!d.a_kc && !d.b_kc) launch_big<false, false, bf16_raw, false, BIG_SEL>(a, grid, st);
+    else return HFTA_EUNSUPPORTED;
+  }
   return launch_status();
 }
 

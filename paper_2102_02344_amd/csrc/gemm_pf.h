@@ -42,17 +42,17 @@ template <bool V16> struct PfOperand<true, V16> {   // k-contiguous: rows t/4 an
       off[h] = r < rows ? (uint32_t)((int64_t)r * ld * 2) + (uint32_t)kg * 2u : PF_OOB;
     }
   }
-  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K, bool live) const {
+  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K) const {
     const int k = k0 + kg;
     if (V16) {
-      const bool ok = live && k + 8 <= K;
+      const bool ok = k + 8 <= K;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(ok ? off[h] + (uint32_t)k0 * 2u : PF_OOB), 0, 0);
         q[h] = make_uint4(v.x, v.y, v.z, v.w);
       }
     } else {
-      const bool ok0 = live && k + 4 <= K, ok1 = live && k + 8 <= K;
+      const bool ok0 = k + 4 <= K, ok1 = k + 8 <= K;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const uint32_t o = off[h] + (uint32_t)k0 * 2u;
@@ -78,11 +78,11 @@ template <bool V16> struct PfOperand<false, V16> {  // m/n-contiguous: 4(k) x 4(
     for (int j = 0; j < 4; ++j)
       off[j] = c + 4 <= cols ? (uint32_t)(kq4 + j) * ldb + (uint32_t)c * 2u : PF_OOB;
   }
-  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K, bool live) const {
+  __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K) const {
     const uint32_t kb = (uint32_t)k0 * ldb;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const bool ok = live && k0 + kq4 + j < K;
+      const bool ok = k0 + kq4 + j < K;
       const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok ? off[j] + kb : PF_OOB), 0, 0);
       q[j] = make_uint2(v.x, v.y);
     }
@@ -136,11 +136,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_pf_kernel(GemmArgs p) {
 
   auto issue = [&](int set, int tt) {
     const bool live = tt < t_end;
+    const int Ke = live ? p.K : 0;      // a dead tile has no valid k: every offset out of range
     const int tc = live ? tt : t_begin;
     const int seg = tc / p.tiles_per_seg;
     const int k0 = (tc - seg * p.tiles_per_seg) * BK;
-    oa.load(ra[set], pf_rsrc(Ab + seg * p.a_ss, p.a_extent), k0, p.K, live);
-    ob.load(rb[set], pf_rsrc(Bb + seg * p.b_ss, p.b_extent), k0, p.K, live);
+    oa.load(ra[set], pf_rsrc(Ab + seg * p.a_ss, p.a_extent), k0, Ke);
+    ob.load(rb[set], pf_rsrc(Bb + seg * p.b_ss, p.b_extent), k0, Ke);
   };
 
   if (t_begin < t_end) {
