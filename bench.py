@@ -33,7 +33,7 @@ class Tracer:
     """Wraps the binding so that selected single-kernel entry points are bracketed
     by HIP events on the stream they launch on (torch's current stream)."""
 
-    SINGLE_KERNEL = ("conv1x1_fwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
+    SINGLE_KERNEL = ("conv1x1_fwd", "conv1x1_bwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
                      "adam_step_multi", "linear_fwd", "bn_fwd_maxpool", "bn_bwd_maxpool")
 
     def __init__(self, hb, torch):
@@ -85,6 +85,9 @@ def kernel_label(name, a):
         return "gemm_pf_kernel(fwd)" if dt == 1 else "gemm_kernel(fwd)"
     if name == "linear_fwd":
         return "gemm_pf_kernel(fwd)" if a[4] == 1 else "gemm_kernel(fwd)"
+    if name == "conv1x1_bwd":          # called with either dX or dW requested, never both
+        k = "gemm_pf_kernel" if a[5] == 1 else "gemm_kernel"
+        return k + ("(dX)" if a[11] is not None else "(dW)+splitk_reduce_kernel")
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
     return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",
@@ -111,6 +114,11 @@ def algorithmic_bytes(name, a):
     if name == "linear_fwd":
         B, M, Fx, Fy, dt = a[:5]
         return B * (M * Fx + Fx * Fy + Fy + M * Fy) * _es(dt)
+    if name == "conv1x1_bwd":
+        B, Nb, Ci, Co, L, dt = a[:6]
+        if a[11] is not None:          # dX = W^T dY: dY and W in, dX out
+            return (B * Nb * (Ci + Co) * L + B * Co * Ci) * _es(dt)
+        return B * Nb * (Ci + Co) * L * _es(dt) + B * Co * Ci * 4      # dW (fp32) = dY X^T
     if name == "maxpool_points":
         B, Nb, C, L, dt = a[:5]
         return B * Nb * C * (L * _es(dt) + _es(dt) + 4)
@@ -187,7 +195,8 @@ def ops_report(torch, binding):
         dW = torch.empty(B, fx, fy, device="cuda")
         ws = torch.empty(max(4, hb.linear_bwd_workspace_bytes(B, M, fx, fy, 1)), dtype=torch.uint8, device="cuda")
         fl = 2.0 * B * M * fx * fy
-        for name, fn in (("linear_fwd+gelu", lambda: hb.linear_fwd(B, M, fx, fy, 1, X, W, bias, Y, hb.ACT_GELU)),
+        for name, fn in (("linear_fwd", lambda: hb.linear_fwd(B, M, fx, fy, 1, X, W, bias, Y)),
+                         ("linear_fwd+gelu", lambda: hb.linear_fwd(B, M, fx, fy, 1, X, W, bias, Y, hb.ACT_GELU)),
                          ("linear_dX", lambda: hb.linear_bwd(B, M, fx, fy, 1, None, W, dY, dX, None, None, None)),
                          ("linear_dW", lambda: hb.linear_bwd(B, M, fx, fy, 1, X, None, dY, None, dW, None, ws))):
             t = timeit(fn)

@@ -274,8 +274,13 @@ class FusedPointNetCls:
                   db=self.g(k + ".bn.b"))
             xin = self.points if i == 0 else self.a[i - 1]
             dxin = None if i == 0 else self.dbuf[cur][:Nb * B * ci * L]
-            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), dz, cs,
-                           dxin, None if i == 0 else _cs(B, ci, L), self.g(k + ".w"), None, self.ws)
+            # data gradient and weight gradient as two calls: one GEMM launch each (plus the weight
+            # gradient's split-K reduction), so a caller can time them separately
+            if i > 0:
+                hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, self.w(k + ".w"), dz, cs,
+                               dxin, _cs(B, ci, L), None, None, None)
+            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), None, dz, cs,
+                           None, None, self.g(k + ".w"), None, self.ws)
             P("conv1x1_bwd", layer=k, x=xin, w=self.w(k + ".w"), dy=dz.view(Nb, B * co, L),
               dx=None if i == 0 else dxin.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"))
             da = dxin

@@ -227,7 +227,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv_gemm_kernel(ConvArgs p) {
     // fp32 output [b][M][N] (contiguous), through the partial buffer when split
     float* base = p.splits > 1 ? p.partial + ((int64_t)split * p.B + b) * (int64_t)p.M * p.N
                                : reinterpret_cast<float*>(p.Out) + (int64_t)b * p.M * p.N;
-    store_tile<float, T>(acc, &smem[0][0][0], base, p.N, p.M, p.N, m0, n0, nullptr, 0, HFTA_ACT_NONE, 0.f, p.c_vec, t);
+    store_tile<float, T, false>(acc, &smem[0][0][0], base, p.N, p.M, p.N, m0, n0, nullptr, 0, HFTA_ACT_NONE, 0.f, p.c_vec, t);
     return;
   }
   // fwd: Y[n][b*Co + m][pix]; dX: dX[n][b*Ci + m][ipx]

@@ -53,6 +53,51 @@ __device__ __forceinline__ float big_act(float x, float neg_slope) {
   return gelu_as(x);
 }
 
+// RP staged rows x 256 columns -> global memory: consecutive lanes on consecutive 16- or 8-byte
+// pieces of a row, so a wavefront's store covers whole row segments.
+template <typename OutT, int THREADS>
+__device__ __forceinline__ void big_store_rows(const unsigned char* smem, OutT* Cb, int64_t c_ld, int M, int N,
+                                               int mbase, int n0, int c_vec, int t) {
+  constexpr int ES = sizeof(OutT);
+  constexpr int RP = ES == 2 ? 128 : 64;
+  constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
+  if (c_vec == 16) {
+    constexpr int EPV = 16 / ES, PPR = 256 / EPV, RPI = THREADS / PPR;
+    const int r0 = t / PPR, c = t % PPR, n = n0 + c * EPV;
+#pragma unroll 4
+    for (int it = 0; it < RP / RPI; ++it) {
+      const int rr = r0 + it * RPI, m = mbase + rr;
+      const uint4 v = *reinterpret_cast<const uint4*>(smem + rr * PITCH + c * 16);
+      OutT* dst = Cb + (int64_t)m * c_ld + n;
+      if (m < M && n + EPV <= N) {
+        *reinterpret_cast<uint4*>(dst) = v;
+      } else if (m < M && n < N) {
+        const OutT* e = reinterpret_cast<const OutT*>(&v);
+#pragma unroll
+        for (int k = 0; k < EPV; ++k)
+          if (n + k < N) dst[k] = e[k];
+      }
+    }
+  } else {
+    constexpr int EPV = 8 / ES, PPR = 256 / EPV, RPI = THREADS / PPR;
+    const int r0 = t / PPR, c = t % PPR, n = n0 + c * EPV;
+#pragma unroll 4
+    for (int it = 0; it < RP / RPI; ++it) {
+      const int rr = r0 + it * RPI, m = mbase + rr;
+      const uint2 v = *reinterpret_cast<const uint2*>(smem + rr * PITCH + c * 8);
+      OutT* dst = Cb + (int64_t)m * c_ld + n;
+      if (m < M && n + EPV <= N && c_vec == 8) {
+        *reinterpret_cast<uint2*>(dst) = v;
+      } else if (m < M && n < N) {
+        const OutT* e = reinterpret_cast<const OutT*>(&v);
+#pragma unroll
+        for (int k = 0; k < EPV; ++k)
+          if (n + k < N) dst[k] = e[k];
+      }
+    }
+  }
+}
+
 // k-contiguous operand: 256 rows x 8 chunks of 16 bytes per k-tile, 4 chunks per thread
 template <bool V16> struct BigOpKc {
   typedef uint4 Regs[4];
@@ -287,43 +332,7 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
       }
     }
     __syncthreads();
-    // RP rows x 256 columns out: consecutive lanes on consecutive pieces of a row
-    const int mbase = m0 + pass * RP;
-    if (p.c_vec == 16) {
-      constexpr int EPV = 16 / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
-      const int r0 = t / PPR, c = t % PPR, n = n0 + c * EPV;
-#pragma unroll 4
-      for (int it = 0; it < RP / RPI; ++it) {
-        const int rr = r0 + it * RPI, m = mbase + rr;
-        const uint4 v = *reinterpret_cast<const uint4*>(smem + rr * PITCH + c * 16);
-        OutT* dst = Cb + (int64_t)m * p.c_ld + n;
-        if (m < p.M && n + EPV <= p.N) {
-          *reinterpret_cast<uint4*>(dst) = v;
-        } else if (m < p.M && n < p.N) {
-          const OutT* e = reinterpret_cast<const OutT*>(&v);
-#pragma unroll
-          for (int k = 0; k < EPV; ++k)
-            if (n + k < p.N) dst[k] = e[k];
-        }
-      }
-    } else {
-      constexpr int EPV = 8 / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
-      const int r0 = t / PPR, c = t % PPR, n = n0 + c * EPV;
-#pragma unroll 4
-      for (int it = 0; it < RP / RPI; ++it) {
-        const int rr = r0 + it * RPI, m = mbase + rr;
-        const uint2 v = *reinterpret_cast<const uint2*>(smem + rr * PITCH + c * 8);
-        OutT* dst = Cb + (int64_t)m * p.c_ld + n;
-        if (m < p.M && n + EPV <= p.N && p.c_vec == 8) {
-          *reinterpret_cast<uint2*>(dst) = v;
-        } else if (m < p.M && n < p.N) {
-          const OutT* e = reinterpret_cast<const OutT*>(&v);
-#pragma unroll
-          for (int k = 0; k < EPV; ++k)
-            if (n + k < p.N) dst[k] = e[k];
-        }
-      }
-    }
+    big_store_rows<OutT, BIG_THREADS>(smem, Cb, p.c_ld, p.M, p.N, m0 + pass * RP, n0, p.c_vec, t);
     if (pass + 1 < 256 / RP) __syncthreads();
   }
 }
