@@ -210,3 +210,71 @@ def dcgan_weights(seed: int, B: int, shape: Sequence[int], dtype: str = "bf16") 
     rngs = model_streams(seed, B)
     w = np.concatenate([r.standard_normal(tuple(shape)) * 0.02 for r in rngs], axis=0)
     return snap(w, dtype)
+
+
+# --------------------------------------------------------------------------
+# Transformer-MLP-block fused array (BASELINE config 4)
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class MlpSpec:
+    """`blocks` residual blocks x <- LayerNorm(x + W2 GELU(W1 x + b1) + b2) on R rows of E features."""
+    name: str
+    B: int
+    R: int                  # rows (tokens) per model per step
+    E: int                  # model width
+    H: int                  # hidden width
+    blocks: int
+    dtype: str
+    Nb: int = 32            # sequences per model per step (R = Nb * tokens per sequence)
+    lr_range: Tuple[float, float] = (1e-5, 1e-3)
+    wd_range: Tuple[float, float] = (0.0, 0.1)
+    config_index: int = 4
+
+
+def spec_c4(B: int = 16, R: int = 4096, E: int = 512, H: int = 2048, blocks: int = 8,
+            dtype: str = "bf16") -> MlpSpec:
+    return MlpSpec(name=f"c4_mlp_blocks_B{B}_{dtype}", B=B, R=R, E=E, H=H, blocks=blocks, dtype=dtype)
+
+
+def mlp_param_shapes(spec: MlpSpec) -> List[Tuple[str, Tuple[int, ...]]]:
+    """Per-model parameter list in arena order; Linear weights are [Fx, Fy] (baddbmm orientation)."""
+    out: List[Tuple[str, Tuple[int, ...]]] = []
+    for i in range(spec.blocks):
+        out += [(f"blk{i}.w1", (spec.E, spec.H)), (f"blk{i}.b1", (spec.H,)),
+                (f"blk{i}.w2", (spec.H, spec.E)), (f"blk{i}.b2", (spec.E,)),
+                (f"blk{i}.ln.w", (spec.E,)), (f"blk{i}.ln.b", (spec.E,))]
+    return out
+
+
+def mlp_inputs(spec: MlpSpec, seed: Optional[int] = None, perturb_ln: bool = False) -> Dict[str, object]:
+    """tokens, targets: float32 [B, R, E] ~ N(0,1) snapped to spec.dtype; params: list over b of
+    dict name -> float32; lr log-uniform, wd uniform, beta = (0.9, 0.999), eps = 1e-8: float32 [B].
+    perturb_ln draws the LayerNorm affine around (1, 0) instead of exactly there (tests)."""
+    seed = config_seed(spec.config_index) if seed is None else seed
+    rngs = model_streams(seed, spec.B)
+    x = np.empty((spec.B, spec.R, spec.E), np.float32)
+    tg = np.empty_like(x)
+    params = []
+    lr = np.empty(spec.B, np.float32)
+    wd = np.empty(spec.B, np.float32)
+    for b, rng in enumerate(rngs):
+        x[b] = rng.standard_normal((spec.R, spec.E))
+        tg[b] = rng.standard_normal((spec.R, spec.E))
+        p = {}
+        for name, shp in mlp_param_shapes(spec):
+            if name.endswith(".ln.w"):
+                p[name] = (1.0 + (0.1 * rng.standard_normal(shp) if perturb_ln else 0.0) * np.ones(shp)).astype(np.float32)
+            elif name.endswith(".ln.b"):
+                p[name] = ((0.1 * rng.standard_normal(shp) if perturb_ln else 0.0) * np.ones(shp)).astype(np.float32)
+            elif len(shp) == 2:
+                p[name] = uniform_fan_in(rng, shp, shp[0], 6.0).astype(np.float32)
+            else:
+                fan_in = spec.E if name.endswith(".b1") else spec.H
+                p[name] = uniform_fan_in(rng, shp, fan_in, 1.0).astype(np.float32)
+        params.append(p)
+        lr[b] = log_uniform(rng, *spec.lr_range)
+        wd[b] = rng.uniform(*spec.wd_range)
+    sd = "f32" if spec.dtype == "f64" else spec.dtype
+    return dict(tokens=snap(x, sd), targets=snap(tg, sd), params=params, lr=lr, wd=wd,
+                beta1=np.full(spec.B, 0.9, np.float32), beta2=np.full(spec.B, 0.999, np.float32),
+                eps=np.full(spec.B, 1e-8, np.float32))

@@ -254,6 +254,10 @@ int hfta_act_fwd(int64_t count, int dtype, const void* X, void* Y, int act, floa
  * RELU, LEAKY with slope > 0, TANH); otherwise Z holds the pre-activation input. */
 int hfta_act_bwd(int64_t count, int dtype, const void* Z, const void* dY, void* dX,
                  int act, float slope, int from_output, void* stream);
+/* Y = A + B element-wise over `count` elements of the storage dtype (the residual connection of
+ * the MLP-block workload; fusion rules table, element-wise operators keep their shape with the
+ * model dimension folded in).  Y may alias A or B.  Device pointers; EINVAL on null / count <= 0. */
+int hfta_add(int64_t count, int dtype, const void* A, const void* B, void* Y, void* stream);
 /* Adds a per-channel bias to an [Nb][K][HW] tensor (K = B*C channels) and applies act, in place. */
 int hfta_bias_act_nchw(int64_t Nb, int64_t K, int64_t HW, int dtype, void* Y, const void* bias,
                        int act, float slope, void* stream);

@@ -62,6 +62,7 @@ _SIGS = {
     "hfta_act_bwd": (_i, [_i64, _i, _p, _p, _p, _i, _f, _i, _p]),
     "hfta_bias_act_nchw": (_i, [_i64, _i64, _i64, _i, _p, _p, _i, _f, _p]),
     "hfta_dropout": (_i, [_i64, _i, _p, _p, _f, _p, _p]),
+    "hfta_add": (_i, [_i64, _i, _p, _p, _p, _p]),
     "hfta_layernorm_fwd": (_i, [_i, _i, _i, _i, _p, _p, _p, _f, _p, _p, _p, _p]),
     "hfta_layernorm_bwd_workspace_bytes": (_sz, [_i, _i, _i]),
     "hfta_layernorm_bwd": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
@@ -239,6 +240,10 @@ def act_bwd(count, dtype, Z, dY, dX, act, slope=0.0, from_output=0, stream=None)
 def bias_act_nchw(Nb, K, HW, dtype, Y, bias, act=ACT_NONE, slope=0.0, stream=None):
     _check(_lib.hfta_bias_act_nchw(Nb, K, HW, dtype, _ptr(Y), _ptr(bias), act, slope, _stream(stream)),
            "hfta_bias_act_nchw")
+
+
+def add(count, dtype, A, B, Y, stream=None):
+    _check(_lib.hfta_add(count, dtype, _ptr(A), _ptr(B), _ptr(Y), _stream(stream)), "hfta_add")
 
 
 def dropout(count, dtype, X, mask, p, Y, stream=None):

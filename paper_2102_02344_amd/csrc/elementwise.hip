@@ -45,6 +45,118 @@ __global__ __launch_bounds__(256) void act_bwd_kernel(const T* __restrict__ z, c
   }
 }
 
+// ---- 16-byte vector forms of the streaming operators ------------------------
+// Used when every pointer is 16-byte aligned (tails run through the element kernels above).  The
+// activation is a template parameter: one scalar branch per element would otherwise cost as much
+// as the memory traffic.  For bf16 storage GELU and its derivative use erf from the
+// Abramowitz-Stegun 7.1.26 rational form (|error| < 1.5e-7) and share one exponential.
+template <typename T> struct V16;
+template <> struct V16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float (&f)[4]) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+  }
+};
+template <> struct V16<bf16_raw> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[2 * i] = __uint_as_float(w[i] << 16); f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+  }
+  static __device__ __forceinline__ uint4 pack(const float (&f)[8]) {
+    return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+  }
+};
+
+// erf(|x|/sqrt 2) and exp(-x^2/2) together
+__device__ __forceinline__ void erf_exp_fast(float x, float& erf_abs, float& ex) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float tt = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.f));
+  float poly = fmaf(tt, 1.061405429f, -1.453152027f);
+  poly = fmaf(tt, poly, 1.421413741f);
+  poly = fmaf(tt, poly, -0.284496736f);
+  poly = fmaf(tt, poly, 0.254829592f);
+  poly *= tt;
+  ex = __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);
+  erf_abs = fmaf(-poly, ex, 1.f);
+}
+
+template <int ACT, bool FAST>
+__device__ __forceinline__ float act_t(float x, float slope) {
+  if (ACT == HFTA_ACT_RELU) return fmaxf(x, 0.f);
+  if (ACT == HFTA_ACT_LEAKY) return x > 0.f ? x : slope * x;
+  if (ACT == HFTA_ACT_TANH) return tanhf(x);
+  if (ACT == HFTA_ACT_GELU) {
+    if (FAST) {
+      float ea, ex;
+      erf_exp_fast(x, ea, ex);
+      return 0.5f * x * (1.f + copysignf(ea, x));
+    }
+    return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
+  }
+  return x;
+}
+template <int ACT, bool FAST>
+__device__ __forceinline__ float act_deriv_t(float x, float slope) {
+  if (ACT == HFTA_ACT_GELU && FAST) {
+    float ea, ex;
+    erf_exp_fast(x, ea, ex);
+    return fmaf(x * 0.39894228040143268f, ex, 0.5f * (1.f + copysignf(ea, x)));
+  }
+  return act_deriv_from_input(x, ACT, slope);
+}
+
+template <typename T, int ACT>
+__global__ __launch_bounds__(256) void act_fwd_vec_kernel(const uint4* __restrict__ x, uint4* __restrict__ y, int64_t nvec, float slope) {
+  constexpr int N = V16<T>::N;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    float f[N];
+    V16<T>::unpack(x[i], f);
+#pragma unroll
+    for (int e = 0; e < N; ++e) f[e] = act_t<ACT, sizeof(T) == 2>(f[e], slope);
+    y[i] = V16<T>::pack(f);
+  }
+}
+
+template <typename T, int ACT, bool FROM_OUT>
+__global__ __launch_bounds__(256) void act_bwd_vec_kernel(const uint4* __restrict__ z, const uint4* __restrict__ dy,
+                                                         uint4* __restrict__ dx, int64_t nvec, float slope) {
+  constexpr int N = V16<T>::N;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    float zz[N], d[N];
+    V16<T>::unpack(z[i], zz);
+    V16<T>::unpack(dy[i], d);
+#pragma unroll
+    for (int e = 0; e < N; ++e)
+      d[e] *= FROM_OUT ? act_deriv_from_output(zz[e], ACT, slope) : act_deriv_t<ACT, sizeof(T) == 2>(zz[e], slope);
+    dx[i] = V16<T>::pack(d);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void add_vec_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
+                                                     uint4* __restrict__ y, int64_t nvec) {
+  constexpr int N = V16<T>::N;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    float fa[N], fb[N];
+    V16<T>::unpack(a[i], fa);
+    V16<T>::unpack(b[i], fb);
+#pragma unroll
+    for (int e = 0; e < N; ++e) fa[e] += fb[e];
+    y[i] = V16<T>::pack(fa);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void add_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    Elem<T>::store(y + i, Elem<T>::load(a + i) + Elem<T>::load(b + i));
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void bias_act_nchw_kernel(T* __restrict__ y, const T* __restrict__ bias, int64_t K, int64_t HW,
                                                            int64_t total, int act, float slope) {
@@ -214,6 +326,34 @@ unsigned stream_blocks(int64_t n) {
   return (unsigned)(b > cap ? cap : (b < 1 ? 1 : b));
 }
 
+
+static inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+template <typename T>
+static void launch_act_fwd_vec(const void* X, void* Y, int64_t nvec, int act, float slope, hipStream_t st) {
+  const dim3 g(stream_blocks(nvec)), b(256);
+  const uint4* x = (const uint4*)X; uint4* y = (uint4*)Y;
+  switch (act) {
+    case HFTA_ACT_RELU: hipLaunchKernelGGL((act_fwd_vec_kernel<T, HFTA_ACT_RELU>), g, b, 0, st, x, y, nvec, slope); break;
+    case HFTA_ACT_LEAKY: hipLaunchKernelGGL((act_fwd_vec_kernel<T, HFTA_ACT_LEAKY>), g, b, 0, st, x, y, nvec, slope); break;
+    case HFTA_ACT_TANH: hipLaunchKernelGGL((act_fwd_vec_kernel<T, HFTA_ACT_TANH>), g, b, 0, st, x, y, nvec, slope); break;
+    case HFTA_ACT_GELU: hipLaunchKernelGGL((act_fwd_vec_kernel<T, HFTA_ACT_GELU>), g, b, 0, st, x, y, nvec, slope); break;
+    default: hipLaunchKernelGGL((act_fwd_vec_kernel<T, HFTA_ACT_NONE>), g, b, 0, st, x, y, nvec, slope); break;
+  }
+}
+template <typename T, bool FROM_OUT>
+static void launch_act_bwd_vec(const void* Z, const void* dY, void* dX, int64_t nvec, int act, float slope, hipStream_t st) {
+  const dim3 g(stream_blocks(nvec)), b(256);
+  const uint4* z = (const uint4*)Z; const uint4* dy = (const uint4*)dY; uint4* dx = (uint4*)dX;
+  switch (act) {
+    case HFTA_ACT_RELU: hipLaunchKernelGGL((act_bwd_vec_kernel<T, HFTA_ACT_RELU, FROM_OUT>), g, b, 0, st, z, dy, dx, nvec, slope); break;
+    case HFTA_ACT_LEAKY: hipLaunchKernelGGL((act_bwd_vec_kernel<T, HFTA_ACT_LEAKY, FROM_OUT>), g, b, 0, st, z, dy, dx, nvec, slope); break;
+    case HFTA_ACT_TANH: hipLaunchKernelGGL((act_bwd_vec_kernel<T, HFTA_ACT_TANH, FROM_OUT>), g, b, 0, st, z, dy, dx, nvec, slope); break;
+    case HFTA_ACT_GELU: hipLaunchKernelGGL((act_bwd_vec_kernel<T, HFTA_ACT_GELU, FROM_OUT>), g, b, 0, st, z, dy, dx, nvec, slope); break;
+    default: hipLaunchKernelGGL((act_bwd_vec_kernel<T, HFTA_ACT_NONE, FROM_OUT>), g, b, 0, st, z, dy, dx, nvec, slope); break;
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -233,12 +373,22 @@ int hfta_version(void) { return 100; }
 
 int hfta_act_fwd(int64_t count, int dtype, const void* X, void* Y, int act, float slope, void* stream) {
   if (count <= 0 || !valid_dtype(dtype) || !X || !Y || !valid_act(act)) return HFTA_EINVAL;
-  if (dtype == HFTA_BF16)
-    hipLaunchKernelGGL(act_fwd_kernel<bf16_raw>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
-                       (const bf16_raw*)X, (bf16_raw*)Y, count, act, slope);
-  else
-    hipLaunchKernelGGL(act_fwd_kernel<float>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
-                       (const float*)X, (float*)Y, count, act, slope);
+  hipStream_t st = as_stream(stream);
+  const int64_t epv = 16 / (int64_t)dtype_size(dtype);
+  const int64_t nvec = (al16(X) && al16(Y)) ? count / epv : 0, done = nvec * epv;
+  if (nvec > 0) {
+    if (dtype == HFTA_BF16) launch_act_fwd_vec<bf16_raw>(X, Y, nvec, act, slope, st);
+    else launch_act_fwd_vec<float>(X, Y, nvec, act, slope, st);
+  }
+  if (done < count) {
+    const int64_t n = count - done;
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(act_fwd_kernel<bf16_raw>, dim3(stream_blocks(n)), dim3(256), 0, st,
+                         (const bf16_raw*)X + done, (bf16_raw*)Y + done, n, act, slope);
+    else
+      hipLaunchKernelGGL(act_fwd_kernel<float>, dim3(stream_blocks(n)), dim3(256), 0, st,
+                         (const float*)X + done, (float*)Y + done, n, act, slope);
+  }
   return launch_status();
 }
 
@@ -246,12 +396,52 @@ int hfta_act_bwd(int64_t count, int dtype, const void* Z, const void* dY, void* 
                  int from_output, void* stream) {
   if (count <= 0 || !valid_dtype(dtype) || !Z || !dY || !dX || !valid_act(act)) return HFTA_EINVAL;
   if (from_output && (act == HFTA_ACT_GELU || (act == HFTA_ACT_LEAKY && !(slope > 0.f)))) return HFTA_EUNSUPPORTED;
-  if (dtype == HFTA_BF16)
-    hipLaunchKernelGGL(act_bwd_kernel<bf16_raw>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
-                       (const bf16_raw*)Z, (const bf16_raw*)dY, (bf16_raw*)dX, count, act, slope, from_output);
-  else
-    hipLaunchKernelGGL(act_bwd_kernel<float>, dim3(stream_blocks(count)), dim3(256), 0, as_stream(stream),
-                       (const float*)Z, (const float*)dY, (float*)dX, count, act, slope, from_output);
+  hipStream_t st = as_stream(stream);
+  const int64_t epv = 16 / (int64_t)dtype_size(dtype);
+  const int64_t nvec = (al16(Z) && al16(dY) && al16(dX)) ? count / epv : 0, done = nvec * epv;
+  if (nvec > 0) {
+    if (dtype == HFTA_BF16) {
+      if (from_output) launch_act_bwd_vec<bf16_raw, true>(Z, dY, dX, nvec, act, slope, st);
+      else launch_act_bwd_vec<bf16_raw, false>(Z, dY, dX, nvec, act, slope, st);
+    } else {
+      if (from_output) launch_act_bwd_vec<float, true>(Z, dY, dX, nvec, act, slope, st);
+      else launch_act_bwd_vec<float, false>(Z, dY, dX, nvec, act, slope, st);
+    }
+  }
+  if (done < count) {
+    const int64_t n = count - done;
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(act_bwd_kernel<bf16_raw>, dim3(stream_blocks(n)), dim3(256), 0, st, (const bf16_raw*)Z + done,
+                         (const bf16_raw*)dY + done, (bf16_raw*)dX + done, n, act, slope, from_output);
+    else
+      hipLaunchKernelGGL(act_bwd_kernel<float>, dim3(stream_blocks(n)), dim3(256), 0, st, (const float*)Z + done,
+                         (const float*)dY + done, (float*)dX + done, n, act, slope, from_output);
+  }
+  return launch_status();
+}
+
+int hfta_add(int64_t count, int dtype, const void* A, const void* Bv, void* Y, void* stream) {
+  if (count <= 0 || !valid_dtype(dtype) || !A || !Bv || !Y) return HFTA_EINVAL;
+  hipStream_t st = as_stream(stream);
+  const int64_t epv = 16 / (int64_t)dtype_size(dtype);
+  const int64_t nvec = (al16(A) && al16(Bv) && al16(Y)) ? count / epv : 0, done = nvec * epv;
+  if (nvec > 0) {
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(add_vec_kernel<bf16_raw>, dim3(stream_blocks(nvec)), dim3(256), 0, st, (const uint4*)A,
+                         (const uint4*)Bv, (uint4*)Y, nvec);
+    else
+      hipLaunchKernelGGL(add_vec_kernel<float>, dim3(stream_blocks(nvec)), dim3(256), 0, st, (const uint4*)A,
+                         (const uint4*)Bv, (uint4*)Y, nvec);
+  }
+  if (done < count) {
+    const int64_t n = count - done;
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(add_kernel<bf16_raw>, dim3(stream_blocks(n)), dim3(256), 0, st, (const bf16_raw*)A + done,
+                         (const bf16_raw*)Bv + done, (bf16_raw*)Y + done, n);
+    else
+      hipLaunchKernelGGL(add_kernel<float>, dim3(stream_blocks(n)), dim3(256), 0, st, (const float*)A + done,
+                         (const float*)Bv + done, (float*)Y + done, n);
+  }
   return launch_status();
 }
 
