@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused training array on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0] [--skip-serial] [--skip-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c4] [--skip-serial] [--skip-cpu]
 
 A step is one forward + backward + Adam pass of the whole fused array over one
 synthetic batch that is already resident in HBM.  Prints ONE JSON line:
@@ -34,7 +34,8 @@ class Tracer:
     by HIP events on the stream they launch on (torch's current stream)."""
 
     SINGLE_KERNEL = ("conv1x1_fwd", "conv1x1_bwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
-                     "adam_step_multi", "linear_fwd", "bn_fwd_maxpool", "bn_bwd_maxpool")
+                     "adam_step_multi", "linear_fwd", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
+                     "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -54,18 +55,19 @@ class Tracer:
             s.record()
             r = fn(*a, **kw)
             e.record()
-            self.events.append((kernel_label(name, a), algorithmic_bytes(name, a), s, e))
+            self.events.append((kernel_label(name, a), algorithmic_bytes(name, a), s, e, algorithmic_flops(name, a)))
             return r
         return wrapped
 
     def summary(self):
         self._torch.cuda.synchronize()
-        tot = defaultdict(lambda: [0, 0.0, 0.0])        # label -> [launches, ms, bytes]
-        for label, nbytes, s, e in self.events:
+        tot = defaultdict(lambda: [0, 0.0, 0.0, 0.0])   # label -> [launches, ms, bytes, flop]
+        for label, nbytes, s, e, fl in self.events:
             t = tot[label]
             t[0] += 1
             t[1] += s.elapsed_time(e)
             t[2] += nbytes
+            t[3] += fl
         return tot
 
 
@@ -84,7 +86,18 @@ def kernel_label(name, a):
             return "conv1x1_stream_kernel"
         return "gemm_pf_kernel(fwd)" if dt == 1 else "gemm_kernel(fwd)"
     if name == "linear_fwd":
+        if a[4] == 1 and big_gemm(a[0], a[1], a[3], a[2]):
+            return "gemm_big_kernel(fwd)"
         return "gemm_pf_kernel(fwd)" if a[4] == 1 else "gemm_kernel(fwd)"
+    if name == "linear_bwd":           # the MLP array asks for dX, dW and dbias in separate calls
+        B, M, Fx, Fy, dt = a[:5]
+        if a[8] is not None:
+            return ("gemm_big_kernel" if dt == 1 and big_gemm(B, M, Fx, Fy) else "gemm_pf_kernel") + "(dX)"
+        if a[9] is not None:
+            return ("gemm_big_kernel" if dt == 1 and big_gemm(B, Fx, Fy, M) else "gemm_pf_kernel") + "(dW)"
+        return "colsum_kernel"
+    if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd"):
+        return name + "_kernel"
     if name == "conv1x1_bwd":          # called with either dX or dW requested, never both
         k = "gemm_pf_kernel" if a[5] == 1 else "gemm_kernel"
         return k + ("(dX)" if a[11] is not None else "(dW)+splitk_reduce_kernel")
@@ -92,6 +105,23 @@ def kernel_label(name, a):
         return name + "_kernel"
     return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",
             "adam_step_multi": "adam_multi_kernel"}[name]
+
+
+def big_gemm(G, M, N, K):
+    """The 256x256-tile kernel's dispatch rule (compute-bound shapes)."""
+    return M >= 192 and N >= 192 and K >= 512 and ((M + 255) // 256) * ((N + 255) // 256) * G >= 192
+
+
+def algorithmic_flops(name, a):
+    if name in ("linear_fwd", "linear_bwd"):
+        B, M, Fx, Fy = a[:4]
+        if name == "linear_bwd" and a[8] is None and a[9] is None:
+            return 0.0
+        return 2.0 * B * M * Fx * Fy
+    if name in ("conv1x1_fwd", "conv1x1_bwd"):
+        B, Nb, Ci, Co, L = a[:5]
+        return 2.0 * B * Nb * Ci * Co * L
+    return 0.0
 
 
 def algorithmic_bytes(name, a):
@@ -119,6 +149,21 @@ def algorithmic_bytes(name, a):
         if a[11] is not None:          # dX = W^T dY: dY and W in, dX out
             return (B * Nb * (Ci + Co) * L + B * Co * Ci) * _es(dt)
         return B * Nb * (Ci + Co) * L * _es(dt) + B * Co * Ci * 4      # dW (fp32) = dY X^T
+    if name == "linear_bwd":
+        B, M, Fx, Fy, dt = a[:5]
+        if a[8] is not None:
+            return B * (M * Fy + Fx * Fy + M * Fx) * _es(dt)
+        if a[9] is not None:
+            return B * (M * Fx + M * Fy) * _es(dt) + B * Fx * Fy * 4
+        return B * M * Fy * _es(dt)
+    if name == "act_fwd":
+        return 2 * a[0] * _es(a[1])
+    if name in ("act_bwd", "add"):
+        return 3 * a[0] * _es(a[1])
+    if name == "layernorm_fwd":
+        return 2 * a[0] * a[1] * a[2] * _es(a[3])
+    if name == "layernorm_bwd":
+        return 3 * a[0] * a[1] * a[2] * _es(a[3])
     if name == "maxpool_points":
         B, Nb, C, L, dt = a[:5]
         return B * Nb * C * (L * _es(dt) + _es(dt) + 4)
@@ -141,27 +186,6 @@ def time_steps(arr, torch, steps, warmup):
         arr.train_step()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps
-
-
-def cpu_baseline(spec, budget_models=1, sample_nb=16):
-    """The oracle as it stands, on a bounded sample: `budget_models` model(s) and
-    `sample_nb` clouds of the full point count; cost is linear in B*Nb."""
-    import hfta_inputs as hi
-    from oracle import pointnet as opn
-    small = dataclasses.replace(spec, B=budget_models, Nb=sample_nb)
-    inp = hi.pointnet_cls_inputs(small)
-    states = [opn.init_state(inp["params"][b]) for b in range(small.B)]
-    t0 = time.perf_counter()
-    opn.array_train_step(small, states, inp, 1)
-    dt = time.perf_counter() - t0
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    return dict(value=small.B * small.Nb / dt, unit="samples/s", cores=int(cores), kind="oracle",
-                sample=f"{small.B} model(s) x {small.Nb} clouds x {small.L} points, one fwd+bwd+Adam step "
-                       f"({dt:.1f} s), numpy float64; host has {os.cpu_count()} logical cores")
 
 
 def ops_report(torch, binding):
@@ -223,12 +247,84 @@ def ops_report(torch, binding):
     return out
 
 
+MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
+BF16_RIDGE = MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # flop per byte above which a GEMM is MFMA-bound
+
+
+class Workload:
+    """What the legs of the benchmark need to know about one BASELINE configuration."""
+
+    def __init__(self, name):
+        import hfta_inputs as hi
+        from paper_2102_02344_amd import arrays
+        self.name = name
+        if name in ("c0", "c1"):
+            from oracle import pointnet as oracle_model
+            self.spec = hi.spec_c1() if name == "c1" else hi.spec_c0()
+            self.inp = hi.pointnet_cls_inputs(self.spec)
+            self.cls = arrays.FusedPointNetCls
+            self.per_model_keys = ("labels",)
+            self.config = {"workload": self.spec.name, "B": self.spec.B, "batch_per_model": self.spec.Nb,
+                           "points": self.spec.L, "conv": list(self.spec.conv), "fc": list(self.spec.fc),
+                           "step": "fwd+bwd+Adam"}
+        else:
+            from oracle import mlp as oracle_model
+            self.spec = hi.spec_c4()
+            self.inp = hi.mlp_inputs(self.spec)
+            self.cls = arrays.FusedMlp
+            self.per_model_keys = ("tokens", "targets")
+            self.config = {"workload": self.spec.name, "B": self.spec.B, "sequences_per_model": self.spec.Nb,
+                           "tokens_per_sequence": self.spec.R // self.spec.Nb, "width": self.spec.E,
+                           "hidden": self.spec.H, "blocks": self.spec.blocks, "step": "fwd+bwd+Adam"}
+        self.oracle = oracle_model
+        self.samples = self.spec.B * self.spec.Nb
+
+    def one_model(self, b):
+        """(spec, inputs) of model b alone: the serial scheme's unit."""
+        s1 = dataclasses.replace(self.spec, B=1)
+        i1 = dict(self.inp)
+        if self.name in ("c0", "c1"):
+            i1["points"] = np.ascontiguousarray(self.inp["points"][:, 3 * b:3 * b + 3])
+            i1["drop_mask"] = None if self.inp["drop_mask"] is None else self.inp["drop_mask"][b:b + 1]
+        for k in self.per_model_keys + ("lr", "beta1", "beta2", "eps", "wd"):
+            i1[k] = self.inp[k][b:b + 1]
+        i1["params"] = self.inp["params"][b:b + 1]
+        return s1, i1
+
+    def cpu_baseline(self):
+        """The oracle as it stands on a bounded sample of one model; its cost is linear in the sample."""
+        import hfta_inputs as hi
+        if self.name in ("c0", "c1"):
+            small = dataclasses.replace(self.spec, B=1, Nb=min(16, self.spec.Nb))
+            inp = hi.pointnet_cls_inputs(small)
+            nsamp = small.Nb
+            what = f"1 model x {small.Nb} clouds x {small.L} points"
+        else:
+            seqs = 4
+            small = dataclasses.replace(self.spec, B=1, R=seqs * (self.spec.R // self.spec.Nb), Nb=seqs)
+            inp = hi.mlp_inputs(small)
+            nsamp = seqs
+            what = f"1 model x {seqs} sequences x {self.spec.R // self.spec.Nb} tokens, {small.blocks} blocks"
+        states = [self.oracle.init_state(inp["params"][0])]
+        t0 = time.perf_counter()
+        self.oracle.array_train_step(small, states, inp, 1)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        return dict(value=nsamp / dt, unit="samples/s", cores=int(cores), kind="oracle",
+                    sample=f"{what}, one fwd+bwd+Adam step ({dt:.1f} s), numpy float64; host has "
+                           f"{os.cpu_count()} logical cores")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c1", choices=["c0", "c1"])
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c4"])
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--ops-report", default=None,
@@ -242,14 +338,13 @@ def main():
         sys.exit(2)
 
     import torch
-    import hfta_inputs as hi
     from paper_2102_02344_amd import arrays, binding
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
-    spec = hi.spec_c1() if args.workload == "c1" else hi.spec_c0()
-    inp = hi.pointnet_cls_inputs(spec)
+    wl = Workload(args.workload)
+    spec, inp = wl.spec, wl.inp
 
     if args.copy_ref:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda")      # 1 GiB read + 1 GiB written
@@ -260,7 +355,7 @@ def main():
 
     tracer = Tracer(binding, torch)
     arrays.hb = tracer
-    arr = arrays.FusedPointNetCls(spec, inp)
+    arr = wl.cls(spec, inp)
     # timed region: trace on, so the dominant kernel's launches are timed inside it
     for _ in range(args.warmup):
         arr.train_step()
@@ -273,60 +368,55 @@ def main():
     sec = (time.perf_counter() - t0) / args.steps
     tracer.enabled = False
     tot = tracer.summary()
-    samples = spec.B * spec.Nb
+    samples = wl.samples
     value = samples / sec
 
     per_kernel = {k: dict(launches_per_step=v[0] // args.steps, ms_per_step=v[1] / args.steps,
-                          GBps=(v[2] / 1e9) / (v[1] / 1e3) if v[1] > 0 else None)
+                          GBps=(v[2] / 1e9) / (v[1] / 1e3) if v[1] > 0 else None,
+                          TFLOPs=(v[3] / 1e12) / (v[1] / 1e3) if v[1] > 0 and v[3] > 0 else None)
                   for k, v in sorted(tot.items(), key=lambda kv: -kv[1][1])}
     dom, dv = max(tot.items(), key=lambda kv: kv[1][1])
-    achieved = (dv[2] / dv[0]) / 1e9 / ((dv[1] / dv[0]) / 1e3)
     # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    # runs of this same command (profiles/c1_pointnet_cls_hbm_traffic.md); null for other workloads
+    # runs of this same command (profiles/<workload>_*_hbm_traffic.md); null when not collected
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "c1_pointnet_cls_traffic.json")
-    if args.workload == "c1" and os.path.exists(tpath):
+    tpath = os.path.join(ROOT, "profiles", f"{args.workload}_traffic.json")
+    if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(dom)
-    roofline = dict(bound="hbm", kernel=dom, achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=traffic,
-                    avg_launch_us=1e3 * dv[1] / dv[0], launches_per_step=dv[0] // args.steps,
-                    algorithmic_bytes_per_launch=dv[2] / dv[0],
-                    share_of_step=(dv[1] / args.steps) / (sec * 1e3))
+    common = dict(kernel=dom, traffic=traffic, avg_launch_us=1e3 * dv[1] / dv[0],
+                  launches_per_step=dv[0] // args.steps, algorithmic_bytes_per_launch=dv[2] / dv[0],
+                  share_of_step=(dv[1] / args.steps) / (sec * 1e3))
+    if dv[3] > 0 and dv[3] / dv[2] > BF16_RIDGE and spec.dtype == "bf16":
+        achieved = (dv[3] / 1e12) / (dv[1] / 1e3)
+        roofline = dict(bound="mfma", achieved=achieved, peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=achieved / MFMA_PEAK_TFLOPS, algorithmic_flop_per_launch=dv[3] / dv[0], **common)
+    else:
+        achieved = (dv[2] / dv[0]) / 1e9 / ((dv[1] / dv[0]) / 1e3)
+        roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=achieved / HBM_PEAK_GBS, **common)
 
     serial = None
     if not args.skip_serial:
         arrays.hb = binding
         per_model = []
-        models = []
-        for b in range(spec.B):
-            s1 = dataclasses.replace(spec, B=1)
-            i1 = dict(inp)
-            i1["points"] = np.ascontiguousarray(inp["points"][:, 3 * b:3 * b + 3])
-            i1["labels"] = inp["labels"][b:b + 1]
-            i1["params"] = inp["params"][b:b + 1]
-            i1["drop_mask"] = None if inp["drop_mask"] is None else inp["drop_mask"][b:b + 1]
-            for k in ("lr", "beta1", "beta2", "eps", "wd"):
-                i1[k] = inp[k][b:b + 1]
-            models.append(arrays.FusedPointNetCls(s1, i1))
         nser = max(3, args.steps // 4)
-        for mdl in models:
+        for b in range(spec.B):          # one model resident at a time: B models, one after another
+            s1, i1 = wl.one_model(b)
+            mdl = wl.cls(s1, i1)
             per_model.append(time_steps(mdl, torch, nser, 2))
-        ssec = sum(per_model)          # B models, one after another
+            del mdl
+        ssec = sum(per_model)
         serial = dict(value=samples / ssec, unit="samples/s", ms_per_step_all_models=ssec * 1e3,
                       fused_speedup=ssec / sec)
-        del models
 
     cpu = None
     if not args.skip_cpu:
-        cpu = cpu_baseline(spec)
+        cpu = wl.cpu_baseline()
 
     out = {
         "metric": "fused train samples/sec summed over B models",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": spec.dtype, "data": "synthetic",
-        "config": {"workload": spec.name, "B": spec.B, "batch_per_model": spec.Nb, "points": spec.L,
-                   "conv": list(spec.conv), "fc": list(spec.fc), "step": "fwd+bwd+Adam"},
+        "dtype": spec.dtype, "data": "synthetic", "config": wl.config,
         "roofline": roofline, "serial_b1": serial, "cpu_baseline": cpu, "kernels": per_kernel,
     }
     if args.ops_report:

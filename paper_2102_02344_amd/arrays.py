@@ -28,7 +28,72 @@ def _cs(B, C, L):
     return (C * L, B * C * L, L, 1)
 
 
-class FusedPointNetCls:
+class ParamArena:
+    """Parameter-major storage of B models' parameters, gradients and Adam state.
+
+    Fused parameter j is one ``[B][n_j]`` tensor (the fusion rules table concatenates weights
+    along the model dimension); the arena is those back to back, so a GEMM sees ``[B][Fx][Fy]`` /
+    ``[B][Co][Ci]`` directly and ONE ``adam_step_multi`` launch walks every parameter of every
+    model with that model's own learning rate, betas and weight decay."""
+
+    def _init_arena(self, shapes, B: int, inp: dict, dtype: str, dev):
+        self.shapes: List[Tuple[str, Tuple[int, ...]]] = shapes
+        self._index = {n: j for j, (n, _) in enumerate(shapes)}
+        off = [0]
+        for _, shp in shapes:
+            off.append(off[-1] + int(np.prod(shp)))
+        self.seg_offsets = off
+        P = off[-1]
+        self.P = P
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.theta = torch.empty(B * P, **f32)
+        self.grad = torch.zeros(B * P, **f32)
+        self.m = torch.zeros(B * P, **f32)
+        self.v = torch.zeros(B * P, **f32)
+        self.lowp = torch.empty(B * P, dtype=torch.bfloat16, device=dev) if dtype == "bf16" else None
+        host = np.empty(B * P, np.float32)
+        for j, (name, shp) in enumerate(shapes):
+            n = off[j + 1] - off[j]
+            blk = np.stack([inp["params"][b][name].reshape(-1) for b in range(B)])
+            host[B * off[j]:B * off[j] + B * n] = blk.reshape(-1)
+        self.theta.copy_(torch.from_numpy(host))
+        if self.lowp is not None:
+            self.lowp.copy_(self.theta)           # initial cast only; afterwards Adam writes it
+        self.hp = {k: torch.from_numpy(np.asarray(inp[k], np.float32)).to(dev)
+                   for k in ("lr", "beta1", "beta2", "eps", "wd")}
+        self.t = 0
+
+    def _seg(self, buf: torch.Tensor, name: str) -> torch.Tensor:
+        j = self._index[name]
+        o, n = self.seg_offsets[j], self.seg_offsets[j + 1] - self.seg_offsets[j]
+        return buf[self.B * o:self.B * (o + n)]
+
+    def w(self, name: str) -> torch.Tensor:
+        """Weights as the GEMMs read them (storage dtype)."""
+        return self._seg(self.lowp if self.lowp is not None else self.theta, name)
+
+    def master(self, name: str) -> torch.Tensor:
+        return self._seg(self.theta, name)
+
+    def g(self, name: str) -> torch.Tensor:
+        return self._seg(self.grad, name)
+
+    def param_host(self, buf: torch.Tensor, name: str, b: int) -> np.ndarray:
+        shp = dict(self.shapes)[name]
+        return self._seg(buf, name).view(self.B, *shp)[b].float().cpu().numpy()
+
+    def adam(self):
+        self.t += 1
+        hb.adam_step_multi(self.B, self.seg_offsets, hb.F32, self.theta, self.grad, self.m, self.v, self.lowp,
+                           self.hp["lr"], self.hp["beta1"], self.hp["beta2"], self.hp["eps"], self.hp["wd"], self.t)
+
+    def train_step(self):
+        loss = self.forward_backward()
+        self.adam()
+        return loss
+
+
+class FusedPointNetCls(ParamArena):
     """PointNet-classification-style array (per-point k=1 convolutions + BatchNorm +
     ReLU, max over points, fully connected head, softmax cross-entropy, Adam)."""
 
@@ -44,32 +109,9 @@ class FusedPointNetCls:
         self.dev = torch.device(device)
         B, Nb, L = self.B, self.Nb, self.L
 
-        # ---- parameter arena (parameter-major) --------------------------------
         import hfta_inputs as hi
-        self.shapes: List[Tuple[str, Tuple[int, ...]]] = hi.pointnet_cls_param_shapes(spec)
-        off = [0]
-        for _, shp in self.shapes:
-            off.append(off[-1] + int(np.prod(shp)))
-        self.seg_offsets = off
-        P = off[-1]
-        self.P = P
+        self._init_arena(hi.pointnet_cls_param_shapes(spec), B, inp, spec.dtype, self.dev)
         f32 = dict(dtype=torch.float32, device=self.dev)
-        self.theta = torch.empty(B * P, **f32)
-        self.grad = torch.zeros(B * P, **f32)
-        self.m = torch.zeros(B * P, **f32)
-        self.v = torch.zeros(B * P, **f32)
-        self.lowp = torch.empty(B * P, dtype=torch.bfloat16, device=self.dev) if spec.dtype == "bf16" else None
-        host = np.empty(B * P, np.float32)
-        for j, (name, shp) in enumerate(self.shapes):
-            n = off[j + 1] - off[j]
-            blk = np.stack([inp["params"][b][name].reshape(-1) for b in range(B)])
-            host[B * off[j]:B * off[j] + B * n] = blk.reshape(-1)
-        self.theta.copy_(torch.from_numpy(host))
-        if self.lowp is not None:
-            self.lowp.copy_(self.theta)           # initial cast only; afterwards Adam writes it
-        self.hp = {k: torch.from_numpy(np.asarray(inp[k], np.float32)).to(self.dev)
-                   for k in ("lr", "beta1", "beta2", "eps", "wd")}
-        self.t = 0
 
         # ---- BatchNorm running statistics / saved statistics -------------------
         self.running: Dict[str, torch.Tensor] = {}
@@ -112,26 +154,6 @@ class FusedPointNetCls:
         self.drop_mask = None
         if spec.dropout_p > 0:
             self.drop_mask = torch.from_numpy(inp["drop_mask"]).to(self.dev)
-
-    # ------------------------------------------------------------------ views
-    def _seg(self, buf: torch.Tensor, name: str) -> torch.Tensor:
-        j = [n for n, _ in self.shapes].index(name)
-        o, n = self.seg_offsets[j], self.seg_offsets[j + 1] - self.seg_offsets[j]
-        return buf[self.B * o:self.B * (o + n)]
-
-    def w(self, name: str) -> torch.Tensor:
-        """Weights as the GEMMs read them (storage dtype)."""
-        return self._seg(self.lowp if self.lowp is not None else self.theta, name)
-
-    def master(self, name: str) -> torch.Tensor:
-        return self._seg(self.theta, name)
-
-    def g(self, name: str) -> torch.Tensor:
-        return self._seg(self.grad, name)
-
-    def param_host(self, buf: torch.Tensor, name: str, b: int) -> np.ndarray:
-        shp = dict(self.shapes)[name]
-        return self._seg(buf, name).view(self.B, *shp)[b].float().cpu().numpy()
 
     # ------------------------------------------------------------------ one step
     def forward_backward(self, probe=None):
@@ -286,12 +308,89 @@ class FusedPointNetCls:
             da = dxin
         return self.loss
 
-    def adam(self):
-        self.t += 1
-        hb.adam_step_multi(self.B, self.seg_offsets, hb.F32, self.theta, self.grad, self.m, self.v, self.lowp,
-                           self.hp["lr"], self.hp["beta1"], self.hp["beta2"], self.hp["eps"], self.hp["wd"], self.t)
 
-    def train_step(self):
-        loss = self.forward_backward()
-        self.adam()
-        return loss
+
+class FusedMlp(ParamArena):
+    """Residual MLP-block array: x <- LayerNorm(x + W2 GELU(W1 x + b1) + b2), `blocks` times, MSE
+    loss per model, Adam with per-model lr and weight decay.  Activations are ``[B, R, F]`` (the
+    fusion rules table's baddbmm layout); every Linear is one batched GEMM over the B weight sets."""
+
+    LN_EPS = 1e-5
+
+    def __init__(self, spec, inp: dict, device: str = "cuda"):
+        import hfta_inputs as hi
+        self.spec = spec
+        self.B, self.R, self.E, self.H = spec.B, spec.R, spec.E, spec.H
+        self.dtype = spec.dtype
+        self.dt = _DT[spec.dtype]
+        self.tdt = _TDT[spec.dtype]
+        self.dev = torch.device(device)
+        B, R, E, H = self.B, self.R, self.E, self.H
+        self._init_arena(hi.mlp_param_shapes(spec), B, inp, spec.dtype, self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        act = dict(dtype=self.tdt, device=self.dev)
+        nb = spec.blocks
+        self.x = [torch.from_numpy(inp["tokens"]).to(self.tdt).to(self.dev)] + \
+                 [torch.empty(B, R, E, **act) for _ in range(nb)]
+        self.target = torch.from_numpy(inp["targets"]).to(self.tdt).to(self.dev)
+        self.u = [torch.empty(B, R, H, **act) for _ in range(nb)]
+        self.h = [torch.empty(B, R, H, **act) for _ in range(nb)]
+        self.s = [torch.empty(B, R, E, **act) for _ in range(nb)]
+        self.y = torch.empty(B, R, E, **act)
+        self.ln_mean = [torch.empty(B * R, **f32) for _ in range(nb)]
+        self.ln_invstd = [torch.empty(B * R, **f32) for _ in range(nb)]
+        self.dE = [torch.empty(B, R, E, **act) for _ in range(3)]
+        self.dH = [torch.empty(B, R, H, **act) for _ in range(2)]
+        self.loss = torch.empty(B, **f32)
+        ws = max(4, hb.layernorm_bwd_workspace_bytes(B, R, E), hb.linear_bwd_workspace_bytes(B, R, E, H, self.dt),
+                 hb.linear_bwd_workspace_bytes(B, R, H, E, self.dt))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+
+    def forward_backward(self, probe=None):
+        """One forward + backward pass; ``probe(op, **tensors)`` as in FusedPointNetCls."""
+        B, R, E, H, dt = self.B, self.R, self.E, self.H, self.dt
+        P = probe if probe is not None else (lambda op, **kw: None)
+        nb = self.spec.blocks
+        for i in range(nb):
+            k = f"blk{i}"
+            x = self.x[i]
+            hb.linear_fwd(B, R, E, H, dt, x, self.w(k + ".w1"), self.w(k + ".b1"), self.u[i])
+            P("linear_fwd", layer=k + ".1", x=x, w=self.w(k + ".w1"), b=self.w(k + ".b1"), y=self.u[i], act=0)
+            hb.act_fwd(B * R * H, dt, self.u[i], self.h[i], hb.ACT_GELU)
+            P("act_fwd", layer=k, x=self.u[i], y=self.h[i], act=hb.ACT_GELU)
+            hb.linear_fwd(B, R, H, E, dt, self.h[i], self.w(k + ".w2"), self.w(k + ".b2"), self.y)
+            P("linear_fwd", layer=k + ".2", x=self.h[i], w=self.w(k + ".w2"), b=self.w(k + ".b2"), y=self.y, act=0)
+            hb.add(B * R * E, dt, x, self.y, self.s[i])
+            P("add", a=x, b=self.y, y=self.s[i])
+            hb.layernorm_fwd(B, R, E, dt, self.s[i], self.master(k + ".ln.w"), self.master(k + ".ln.b"), self.LN_EPS,
+                             self.ln_mean[i], self.ln_invstd[i], self.x[i + 1])
+            P("layernorm_fwd", layer=k, x=self.s[i], w=self.master(k + ".ln.w"), b=self.master(k + ".ln.b"),
+              y=self.x[i + 1], mean=self.ln_mean[i], invstd=self.ln_invstd[i])
+        d = self.dE[0]
+        hb.mse(B, R * E, dt, self.x[nb], self.target, self.loss, d)
+        P("mse", pred=self.x[nb], target=self.target, loss=self.loss, d=d)
+        cur = 0
+        for i in reversed(range(nb)):
+            k = f"blk{i}"
+            ds, dxl = self.dE[(cur + 1) % 3], self.dE[(cur + 2) % 3]
+            hb.layernorm_bwd(B, R, E, dt, self.s[i], d, self.master(k + ".ln.w"), self.ln_mean[i], self.ln_invstd[i],
+                             ds, self.g(k + ".ln.w"), self.g(k + ".ln.b"), self.ws)
+            P("layernorm_bwd", layer=k, x=self.s[i], dy=d, w=self.master(k + ".ln.w"), mean=self.ln_mean[i],
+              invstd=self.ln_invstd[i], dx=ds, dw=self.g(k + ".ln.w"), db=self.g(k + ".ln.b"))
+            # data gradient, weight gradient and bias gradient as separate calls (one kernel each),
+            # so a caller can time them separately
+            hb.linear_bwd(B, R, H, E, dt, None, self.w(k + ".w2"), ds, self.dH[0], None, None, None)
+            hb.linear_bwd(B, R, H, E, dt, self.h[i], None, ds, None, self.g(k + ".w2"), None, self.ws)
+            hb.linear_bwd(B, R, H, E, dt, None, None, ds, None, None, self.g(k + ".b2"), None)
+            P("linear_bwd", layer=k + ".2", x=self.h[i], w=self.w(k + ".w2"), dy=ds, dx=self.dH[0],
+              dw=self.g(k + ".w2"), db=self.g(k + ".b2"))
+            hb.act_bwd(B * R * H, dt, self.u[i], self.dH[0], self.dH[1], hb.ACT_GELU)
+            P("act_bwd", layer=k, x=self.u[i], dy=self.dH[0], dx=self.dH[1], act=hb.ACT_GELU)
+            hb.linear_bwd(B, R, E, H, dt, None, self.w(k + ".w1"), self.dH[1], dxl, None, None, None)
+            hb.linear_bwd(B, R, E, H, dt, self.x[i], None, self.dH[1], None, self.g(k + ".w1"), None, self.ws)
+            hb.linear_bwd(B, R, E, H, dt, None, None, self.dH[1], None, None, self.g(k + ".b1"), None)
+            P("linear_bwd", layer=k + ".1", x=self.x[i], w=self.w(k + ".w1"), dy=self.dH[1], dx=dxl,
+              dw=self.g(k + ".w1"), db=self.g(k + ".b1"))
+            hb.add(B * R * E, dt, ds, dxl, d)          # d (this block's incoming gradient) is dead: reuse it
+            P("add", a=ds, b=dxl, y=d)
+        return self.loss

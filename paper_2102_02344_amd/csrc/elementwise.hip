@@ -257,6 +257,136 @@ __global__ __launch_bounds__(256) void layernorm_bwd_reduce_kernel(const float* 
   db[(int64_t)b * E + e] = ab;
 }
 
+// ---- LayerNorm, register-resident rows ----------------------------------------
+// One wavefront per row, a lane holds CH x 16 bytes of it (E <= CH * 64 * 16 / sizeof(T)), so the
+// row is read from memory once: statistics, normalisation (and in the backward the per-column
+// partial sums for dw, db) all work on registers.  Rows of a block are dealt round-robin to its
+// four wavefronts; column partials are combined wave 0..3 in order, so results are reproducible.
+template <typename T, int CH>
+__global__ __launch_bounds__(256) void layernorm_fwd_vec_kernel(const uint4* __restrict__ X, const float* __restrict__ w,
+                                                               const float* __restrict__ bsh, float eps,
+                                                               float* __restrict__ save_mean, float* __restrict__ save_invstd,
+                                                               uint4* __restrict__ Y, int R, int E, int64_t rows) {
+  constexpr int N = V16<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int b = (int)(row / R);
+  const int vpr = E / N;                                  // 16-byte vectors per row
+  float f[CH][N];
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const int v = lane + 64 * c;
+    if (v < vpr) {
+      V16<T>::unpack(X[row * vpr + v], f[c]);
+#pragma unroll
+      for (int e = 0; e < N; ++e) s += f[c][e];
+    }
+  }
+  const float mean = wave_sum(s) / (float)E;
+  float q = 0.f;
+#pragma unroll
+  for (int c = 0; c < CH; ++c)
+    if (lane + 64 * c < vpr) {
+#pragma unroll
+      for (int e = 0; e < N; ++e) { const float d = f[c][e] - mean; q = fmaf(d, d, q); }
+    }
+  const float invstd = 1.0f / sqrtf(wave_sum(q) / (float)E + eps);
+  if (lane == 0) { save_mean[row] = mean; save_invstd[row] = invstd; }
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const int v = lane + 64 * c;
+    if (v < vpr) {
+      const float* wp = w + (int64_t)b * E + v * N;
+      const float* bp = bsh + (int64_t)b * E + v * N;
+#pragma unroll
+      for (int e = 0; e < N; ++e) f[c][e] = fmaf((f[c][e] - mean) * invstd, wp[e], bp[e]);
+      Y[row * vpr + v] = V16<T>::pack(f[c]);
+    }
+  }
+}
+
+template <typename T, int CH>
+__global__ __launch_bounds__(256) void layernorm_bwd_vec_kernel(const uint4* __restrict__ X, const uint4* __restrict__ dY,
+                                                               const float* __restrict__ w, const float* __restrict__ save_mean,
+                                                               const float* __restrict__ save_invstd, uint4* __restrict__ dX,
+                                                               float* __restrict__ part, int R, int E, int rows_per_block) {
+  constexpr int N = V16<T>::N;
+  __shared__ float red[3][2][CH * 64 * N];                // waves 1..3: [dw | db] partials
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int b = blockIdx.y;
+  const int r_begin = blockIdx.x * rows_per_block;
+  const int r_end = min(R, r_begin + rows_per_block);
+  const int vpr = E / N;
+  float wl[CH][N], aw[CH][N], ab[CH][N];
+#pragma unroll
+  for (int c = 0; c < CH; ++c)
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      const int col = (lane + 64 * c) * N + e;
+      wl[c][e] = col < E ? w[(int64_t)b * E + col] : 0.f;
+      aw[c][e] = 0.f; ab[c][e] = 0.f;
+    }
+  for (int r = r_begin + wv; r < r_end; r += 4) {
+    const int64_t row = (int64_t)b * R + r;
+    const float mean = save_mean[row], invstd = save_invstd[row];
+    float xh[CH][N], g[CH][N];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int v = lane + 64 * c;
+      if (v < vpr) {
+        float x[N], d[N];
+        V16<T>::unpack(X[row * vpr + v], x);
+        V16<T>::unpack(dY[row * vpr + v], d);
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+          xh[c][e] = (x[e] - mean) * invstd;
+          g[c][e] = d[e] * wl[c][e];
+          s1 += g[c][e]; s2 = fmaf(g[c][e], xh[c][e], s2);
+          aw[c][e] = fmaf(d[e], xh[c][e], aw[c][e]); ab[c][e] += d[e];
+        }
+      }
+    }
+    s1 = wave_sum(s1) / (float)E;
+    s2 = wave_sum(s2) / (float)E;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int v = lane + 64 * c;
+      if (v < vpr) {
+        float o[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) o[e] = invstd * (g[c][e] - s1 - xh[c][e] * s2);
+        dX[row * vpr + v] = V16<T>::pack(o);
+      }
+    }
+  }
+  if (wv > 0) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        red[wv - 1][0][(lane + 64 * c) * N + e] = aw[c][e];
+        red[wv - 1][1][(lane + 64 * c) * N + e] = ab[c][e];
+      }
+  }
+  __syncthreads();
+  if (wv == 0) {
+    float* pw = part + (((int64_t)b * gridDim.x + blockIdx.x) * 2) * E;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        const int col = (lane + 64 * c) * N + e;
+        if (col < E) {
+          pw[col] = ((aw[c][e] + red[0][0][col]) + red[1][0][col]) + red[2][0][col];
+          pw[E + col] = ((ab[c][e] + red[0][1][col]) + red[1][1][col]) + red[2][1][col];
+        }
+      }
+  }
+}
+
 // ---- losses: one workgroup per model, fixed reduction order ----------------
 __device__ __forceinline__ float block_sum_1024(float v, float* sh) {
   v = wave_sum(v);
@@ -477,6 +607,19 @@ int hfta_layernorm_fwd(int B, int R, int E, int dtype, const void* X, const floa
   const int64_t rows = (int64_t)B * R;
   if ((rows + 3) / 4 > 0x7fffffffLL) return HFTA_EINVAL;
   dim3 grid((unsigned)((rows + 3) / 4));
+  const int epv = 16 / (int)dtype_size(dtype);
+  if (al16(X) && al16(Y) && E % epv == 0 && E / epv <= 128) {      // rows fit one or two 16-byte pieces per lane
+    hipStream_t st = as_stream(stream);
+    const bool one = E / epv <= 64;
+    if (dtype == HFTA_BF16) {
+      if (one) hipLaunchKernelGGL((layernorm_fwd_vec_kernel<bf16_raw, 1>), grid, dim3(256), 0, st, (const uint4*)X, w, b, eps, save_mean, save_invstd, (uint4*)Y, R, E, rows);
+      else hipLaunchKernelGGL((layernorm_fwd_vec_kernel<bf16_raw, 2>), grid, dim3(256), 0, st, (const uint4*)X, w, b, eps, save_mean, save_invstd, (uint4*)Y, R, E, rows);
+    } else {
+      if (one) hipLaunchKernelGGL((layernorm_fwd_vec_kernel<float, 1>), grid, dim3(256), 0, st, (const uint4*)X, w, b, eps, save_mean, save_invstd, (uint4*)Y, R, E, rows);
+      else hipLaunchKernelGGL((layernorm_fwd_vec_kernel<float, 2>), grid, dim3(256), 0, st, (const uint4*)X, w, b, eps, save_mean, save_invstd, (uint4*)Y, R, E, rows);
+    }
+    return launch_status();
+  }
   if (dtype == HFTA_BF16)
     hipLaunchKernelGGL(layernorm_fwd_kernel<bf16_raw>, grid, dim3(256), 0, as_stream(stream), (const bf16_raw*)X, w, b, eps,
                        save_mean, save_invstd, (bf16_raw*)Y, R, E, rows);
@@ -507,7 +650,18 @@ int hfta_layernorm_bwd(int B, int R, int E, int dtype, const void* X, const void
   const int rpb = (R + nblk - 1) / nblk;
   hipStream_t st = as_stream(stream);
   dim3 grid((unsigned)nblk, (unsigned)B);
-  if (dtype == HFTA_BF16)
+  const int epv = 16 / (int)dtype_size(dtype);
+  if (al16(X) && al16(dY) && al16(dX) && E % epv == 0 && E / epv <= 128) {
+    const bool one = E / epv <= 64;
+    float* part = (float*)workspace;
+    if (dtype == HFTA_BF16) {
+      if (one) hipLaunchKernelGGL((layernorm_bwd_vec_kernel<bf16_raw, 1>), grid, dim3(256), 0, st, (const uint4*)X, (const uint4*)dY, w, save_mean, save_invstd, (uint4*)dX, part, R, E, rpb);
+      else hipLaunchKernelGGL((layernorm_bwd_vec_kernel<bf16_raw, 2>), grid, dim3(256), 0, st, (const uint4*)X, (const uint4*)dY, w, save_mean, save_invstd, (uint4*)dX, part, R, E, rpb);
+    } else {
+      if (one) hipLaunchKernelGGL((layernorm_bwd_vec_kernel<float, 1>), grid, dim3(256), 0, st, (const uint4*)X, (const uint4*)dY, w, save_mean, save_invstd, (uint4*)dX, part, R, E, rpb);
+      else hipLaunchKernelGGL((layernorm_bwd_vec_kernel<float, 2>), grid, dim3(256), 0, st, (const uint4*)X, (const uint4*)dY, w, save_mean, save_invstd, (uint4*)dX, part, R, E, rpb);
+    }
+  } else if (dtype == HFTA_BF16)
     hipLaunchKernelGGL(layernorm_bwd_kernel<bf16_raw>, grid, dim3(256), 0, st, (const bf16_raw*)X, (const bf16_raw*)dY, w,
                        save_mean, save_invstd, (bf16_raw*)dX, (float*)workspace, R, E, rpb);
   else

@@ -31,6 +31,52 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ dY, f
     out[(int64_t)b * Fy + col] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
 }
 
+// The same with 16-byte loads: 1024 threads = 16 column groups (one 16-byte piece of a row each,
+// so a row's pieces are contiguous) x 64 row lanes; row lanes are summed through LDS in a fixed
+// order.  Needs Fy a multiple of the piece and 16-byte aligned rows.
+template <typename T>
+__global__ __launch_bounds__(1024) void colsum_vec_kernel(const uint4* __restrict__ dY, float* __restrict__ out,
+                                                         int M, int Fy) {
+  constexpr int N = 16 / sizeof(T);
+  __shared__ float part[64][16 * N + 1];
+  const int b = blockIdx.y;
+  const int cg = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const int vpr = Fy / N;
+  const int v = blockIdx.x * 16 + cg;
+  float acc[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) acc[e] = 0.f;
+  if (v < vpr) {
+    const uint4* p = dY + (int64_t)b * M * vpr + v;
+#pragma unroll 4
+    for (int r = rl; r < M; r += 64) {
+      const uint4 q = p[(int64_t)r * vpr];
+      if (sizeof(T) == 2) {
+        const uint32_t wds[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[(2 * i) % N] += __uint_as_float(wds[i] << 16);
+          acc[(2 * i + 1) % N] += __uint_as_float(wds[i] & 0xffff0000u);
+        }
+      } else {
+        acc[0] += __uint_as_float(q.x); acc[1 % N] += __uint_as_float(q.y);
+        acc[2 % N] += __uint_as_float(q.z); acc[3 % N] += __uint_as_float(q.w);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) part[rl][cg * N + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < 16 * N) {
+    const int col = blockIdx.x * 16 * N + threadIdx.x;
+    if (col < Fy) {
+      float s = 0.f;
+      for (int r = 0; r < 64; ++r) s += part[r][threadIdx.x];
+      out[(int64_t)b * Fy + col] = s;
+    }
+  }
+}
+
 // dbias of the fused conv: sum over (n, l) of dY[b, n, o, :]; one workgroup per (o, b).
 template <typename T>
 __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ dY, float* __restrict__ out,
@@ -139,6 +185,15 @@ int hfta_linear_bwd(int B, int M, int Fx, int Fy, int dtype, const void* X, cons
   }
   if (dbias) {
     dim3 grid((unsigned)((Fy + 63) / 64), (unsigned)B);
+    const int epv = 16 / (int)dtype_size(dtype);
+    if (Fy % epv == 0 && (reinterpret_cast<uintptr_t>(dY) & 15) == 0 && M >= 64) {
+      dim3 vgrid((unsigned)((Fy / epv + 15) / 16), (unsigned)B);
+      if (dtype == HFTA_BF16)
+        hipLaunchKernelGGL(colsum_vec_kernel<bf16_raw>, vgrid, dim3(1024), 0, st, (const uint4*)dY, dbias, M, Fy);
+      else
+        hipLaunchKernelGGL(colsum_vec_kernel<float>, vgrid, dim3(1024), 0, st, (const uint4*)dY, dbias, M, Fy);
+      return launch_status();
+    }
     if (dtype == HFTA_BF16)
       hipLaunchKernelGGL(colsum_kernel<bf16_raw>, grid, dim3(256), 0, st, (const bf16_raw*)dY, dbias, M, Fy);
     else

@@ -1,0 +1,144 @@
+"""Whole-step parity of the fused residual MLP-block array (the Linear-heavy workload) against B
+separate unfused oracle runs: every library call checked in place on the bits it consumed, the
+free-running chain checked at a tolerance that grows with the number of calls, fused == serial."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import hfta_inputs as hi
+from oracle import array as oa
+from oracle import mlp as omlp
+from oracle import ops as oops
+from util import TOL, check
+
+pytestmark = pytest.mark.gpu
+
+
+def small(dtype, B=3, R=200, E=72, H=136, blocks=2):
+    return hi.MlpSpec(name=f"mlp_small_{dtype}", B=B, R=R, E=E, H=H, blocks=blocks, dtype=dtype, Nb=1)
+
+
+def H64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def probe_for(spec, seen):
+    B, tol = spec.B, TOL[spec.dtype]
+
+    def probe(op, **kw):
+        torch.cuda.synchronize()
+        seen.append(op)
+        lay = kw.get("layer", "")
+        if op == "linear_fwd":
+            check(H64(kw["y"]), oa.linear_fwd(B, H64(kw["x"]), H64(kw["w"]).reshape(B, kw["x"].shape[2], -1), H64(kw["b"]).reshape(B, -1)),
+                  tol, f"{lay} linear fwd")
+        elif op == "act_fwd":
+            check(H64(kw["y"]), oops.act_fwd(H64(kw["x"]), oops.ACT_GELU), tol, f"{lay} gelu")
+        elif op == "add":
+            check(H64(kw["y"]), H64(kw["a"]) + H64(kw["b"]), tol, "add")
+        elif op == "layernorm_fwd":
+            E = kw["x"].shape[2]
+            y, mean, invstd = oa.layernorm_fwd(B, H64(kw["x"]), H64(kw["w"]).reshape(B, E), H64(kw["b"]).reshape(B, E), 1e-5)
+            check(H64(kw["y"]), y, tol, f"{lay} ln")
+            check(H64(kw["mean"]).reshape(B, -1), mean, 1e-5, f"{lay} ln mean")
+            check(H64(kw["invstd"]).reshape(B, -1), invstd, 1e-5, f"{lay} ln invstd")
+        elif op == "mse":
+            for b in range(B):
+                loss, d = oops.mse(H64(kw["pred"])[b], H64(kw["target"])[b])
+                assert abs(float(kw["loss"][b]) - loss) <= 1e-5 * abs(loss) + 1e-12
+                check(H64(kw["d"])[b], d, tol, "mse grad")
+        elif op == "layernorm_bwd":
+            E = kw["x"].shape[2]
+            dx, dw, db = oa.layernorm_bwd(B, H64(kw["x"]), H64(kw["dy"]), H64(kw["w"]).reshape(B, E),
+                                          H64(kw["mean"]).reshape(B, -1), H64(kw["invstd"]).reshape(B, -1))
+            check(H64(kw["dx"]), dx, tol, f"{lay} ln dx")
+            check(H64(kw["dw"]).reshape(B, E), dw, 1e-5 if spec.dtype == "f32" else 2e-4, f"{lay} ln dw")
+            check(H64(kw["db"]).reshape(B, E), db, 1e-5 if spec.dtype == "f32" else 2e-4, f"{lay} ln db")
+        elif op == "linear_bwd":
+            Fx, Fy = kw["x"].shape[2], kw["dy"].shape[2]
+            dx, dw, db = oa.linear_bwd(B, H64(kw["x"]), H64(kw["w"]).reshape(B, Fx, Fy), H64(kw["dy"]))
+            ftol = 1e-5 if spec.dtype == "f32" else 2e-4          # fp32 outputs of bf16 operands
+            check(H64(kw["dx"]), dx, tol, f"{lay} linear dx")
+            check(H64(kw["dw"]).reshape(B, Fx, Fy), dw, ftol, f"{lay} linear dw")
+            check(H64(kw["db"]).reshape(B, Fy), db, ftol, f"{lay} linear db")
+        elif op == "act_bwd":
+            check(H64(kw["dx"]), oops.act_bwd(H64(kw["x"]), H64(kw["dy"]), oops.ACT_GELU), tol, f"{lay} gelu bwd")
+        else:
+            raise AssertionError(op)
+    return probe
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_call_in_place(dtype):
+    from paper_2102_02344_amd.arrays import FusedMlp
+    spec = small(dtype)
+    inp = hi.mlp_inputs(spec, seed=41, perturb_ln=True)
+    arr = FusedMlp(spec, inp)
+    seen = []
+    arr.forward_backward(probe_for(spec, seen))
+    assert seen.count("linear_fwd") == 2 * spec.blocks and seen.count("linear_bwd") == 2 * spec.blocks
+    assert seen.count("layernorm_bwd") == spec.blocks and seen.count("add") == 2 * spec.blocks
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_free_running_steps_match_the_oracle(dtype):
+    from paper_2102_02344_amd.arrays import FusedMlp
+    spec = small(dtype)
+    inp = hi.mlp_inputs(spec, seed=42, perturb_ln=True)
+    arr = FusedMlp(spec, inp)
+    states = [omlp.init_state(p) for p in inp["params"]]
+    calls = 9 * spec.blocks + 1
+    tol = (1e-5 if dtype == "f32" else 2e-2) * (calls if dtype == "f32" else 3)
+    for t in (1, 2):
+        outs = omlp.array_train_step(spec, states, inp, t)
+        arr.forward_backward()
+        torch.cuda.synchronize()
+        loss = arr.loss.cpu().numpy()
+        for b in range(spec.B):
+            assert abs(loss[b] - outs[b]["loss"]) <= tol * abs(outs[b]["loss"]), (b, loss[b], outs[b]["loss"])
+            for name, _ in arr.shapes:
+                g = arr.param_host(arr.grad, name, b).astype(np.float64)
+                ref = outs[b]["grads"][name]
+                err = np.abs(g - ref).max() / max(np.abs(ref).max(), 1e-30)
+                assert err <= tol, (name, b, t, err)
+        arr.adam()
+        torch.cuda.synchronize()
+        for b in range(spec.B):
+            lr = float(inp["lr"][b])
+            for name, _ in arr.shapes:
+                th = arr.param_host(arr.theta, name, b).astype(np.float64)
+                ref = states[b]["theta"][name].astype(np.float64)
+                gref = outs[b]["grads"][name]
+                ok = np.abs(gref) >= 1e-2 * np.abs(gref).max()
+                assert np.abs(th - ref)[ok].max() <= max(tol * np.abs(ref).max(), 10 * tol * lr * t), (name, b, t)
+                assert np.abs(th - ref).max() <= 2.5 * lr * t, (name, b, t)
+
+
+def test_fused_array_equals_models_run_alone():
+    """Model b inside the B-array and the same model run through the library with B = 1 (the serial
+    scheme) see the same kernels on the same numbers: per-model results must agree to rounding."""
+    from paper_2102_02344_amd.arrays import FusedMlp
+    spec = small("bf16", B=3)
+    inp = hi.mlp_inputs(spec, seed=43, perturb_ln=True)
+    arr = FusedMlp(spec, inp)
+    arr.train_step()
+    torch.cuda.synchronize()
+    for b in range(spec.B):
+        i1 = dict(inp)
+        for k in ("tokens", "targets", "lr", "wd", "beta1", "beta2", "eps"):
+            i1[k] = inp[k][b:b + 1]
+        i1["params"] = inp["params"][b:b + 1]
+        one = FusedMlp(dataclasses.replace(spec, B=1), i1)
+        one.train_step()
+        torch.cuda.synchronize()
+        assert abs(float(one.loss[0]) - float(arr.loss[b])) <= 1e-6 * abs(float(arr.loss[b]))
+        for name, _ in arr.shapes:
+            a = arr.param_host(arr.theta, name, b)
+            o = one.param_host(one.theta, name, 0)
+            ga = arr.param_host(arr.grad, name, b)
+            go = one.param_host(one.grad, name, 0)
+            assert np.abs(ga - go).max() <= 1e-5 * max(np.abs(ga).max(), 1e-30), name
+            # Adam's first step is lr * sign(g) wherever |g| >> eps: a sign can flip at g ~ 0
+            assert np.abs(a - o).max() <= 2.5 * float(inp["lr"][b]), name
