@@ -278,3 +278,81 @@ def mlp_inputs(spec: MlpSpec, seed: Optional[int] = None, perturb_ln: bool = Fal
     return dict(tokens=snap(x, sd), targets=snap(tg, sd), params=params, lr=lr, wd=wd,
                 beta1=np.full(spec.B, 0.9, np.float32), beta2=np.full(spec.B, 0.999, np.float32),
                 eps=np.full(spec.B, 1e-8, np.float32))
+
+
+# --------------------------------------------------------------------------
+# DCGAN-style fused array (BASELINE config 3)
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class DcganSpec:
+    """B generator/discriminator pairs; layers as (Ci, Co, H_in, stride, pad), 4x4 kernels."""
+    name: str
+    B: int
+    Nb: int                          # images per model per step
+    g_layers: Tuple[Tuple[int, int, int, int, int], ...]
+    d_layers: Tuple[Tuple[int, int, int, int, int], ...]
+    dtype: str
+    lr_range: Tuple[float, float] = (1e-4, 5e-4)
+    config_index: int = 3
+
+
+def spec_c3(B: int = 10, Nb: int = 64, dtype: str = "bf16") -> DcganSpec:
+    return DcganSpec(name=f"c3_dcgan_B{B}_{dtype}", B=B, Nb=Nb, g_layers=DCGAN_G_LAYERS,
+                     d_layers=DCGAN_D_LAYERS, dtype=dtype)
+
+
+def dcgan_thin(B: int, Nb: int, dtype: str, div: int = 16, cz: int = 12) -> DcganSpec:
+    """The same 64x64 architecture with every channel count divided by `div` (tests)."""
+    g = tuple((cz if i == 0 else max(ci // div, 2), co if i == 4 else max(co // div, 2), h, s, p)
+              for i, (ci, co, h, s, p) in enumerate(DCGAN_G_LAYERS))
+    d = tuple((ci if i == 0 else max(ci // div, 2), co if i == 4 else max(co // div, 2), h, s, p)
+              for i, (ci, co, h, s, p) in enumerate(DCGAN_D_LAYERS))
+    return DcganSpec(name=f"dcgan_thin{div}_B{B}_{dtype}", B=B, Nb=Nb, g_layers=g, d_layers=d, dtype=dtype)
+
+
+def dcgan_param_shapes(spec: DcganSpec):
+    """(generator list, discriminator list) of (name, shape) per model, arena order.
+    ConvTranspose weights are [Cin, Cout, 4, 4], Conv weights [Cout, Cin, 4, 4]."""
+    g, d = [], []
+    for i, (ci, co, _, _, _) in enumerate(spec.g_layers):
+        g.append((f"g{i}.w", (ci, co, 4, 4)))
+        if i < len(spec.g_layers) - 1:
+            g += [(f"g{i}.bn.g", (co,)), (f"g{i}.bn.b", (co,))]
+    for i, (ci, co, _, _, _) in enumerate(spec.d_layers):
+        d.append((f"d{i}.w", (co, ci, 4, 4)))
+        if 0 < i < len(spec.d_layers) - 1:
+            d += [(f"d{i}.bn.g", (co,)), (f"d{i}.bn.b", (co,))]
+    return g, d
+
+
+def dcgan_inputs(spec: DcganSpec, seed: Optional[int] = None) -> Dict[str, object]:
+    """z: float32 [Nb, B*Cz, 1, 1] ~ N(0,1); real: [Nb, B*3, 64, 64] ~ U(-1,1) (both snapped to the
+    storage dtype); gparams / dparams: lists over b of dict name -> float32 (weights N(0, 0.02^2),
+    BatchNorm scale N(1, 0.02^2), shift 0); lr log-uniform per model, beta = (0.5, 0.999), eps 1e-8, wd 0."""
+    seed = config_seed(spec.config_index) if seed is None else seed
+    rngs = model_streams(seed, spec.B)
+    cz = spec.g_layers[0][0]
+    H = spec.d_layers[0][2]
+    z = np.empty((spec.Nb, spec.B * cz, 1, 1), np.float32)
+    real = np.empty((spec.Nb, spec.B * 3, H, H), np.float32)
+    gsh, dsh = dcgan_param_shapes(spec)
+    gparams, dparams = [], []
+    lr = np.empty(spec.B, np.float32)
+    for b, rng in enumerate(rngs):
+        z[:, cz * b:cz * (b + 1)] = rng.standard_normal((spec.Nb, cz, 1, 1))
+        real[:, 3 * b:3 * b + 3] = rng.uniform(-1.0, 1.0, (spec.Nb, 3, H, H))
+        for shapes, out in ((gsh, gparams), (dsh, dparams)):
+            p = {}
+            for name, shp in shapes:
+                if name.endswith(".bn.g"):
+                    p[name] = (1.0 + 0.02 * rng.standard_normal(shp)).astype(np.float32)
+                elif name.endswith(".bn.b"):
+                    p[name] = np.zeros(shp, np.float32)
+                else:
+                    p[name] = (0.02 * rng.standard_normal(shp)).astype(np.float32)
+            out.append(p)
+        lr[b] = log_uniform(rng, *spec.lr_range)
+    sd = "f32" if spec.dtype == "f64" else spec.dtype
+    return dict(z=snap(z, sd), real=snap(real, sd), gparams=gparams, dparams=dparams, lr=lr,
+                beta1=np.full(spec.B, 0.5, np.float32), beta2=np.full(spec.B, 0.999, np.float32),
+                eps=np.full(spec.B, 1e-8, np.float32), wd=np.zeros(spec.B, np.float32))
