@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused training array on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c4] [--skip-serial] [--skip-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c3|c4] [--skip-serial] [--skip-cpu]
 
 A step is one forward + backward + Adam pass of the whole fused array over one
 synthetic batch that is already resident in HBM.  Prints ONE JSON line:
@@ -35,7 +35,8 @@ class Tracer:
 
     SINGLE_KERNEL = ("conv1x1_fwd", "conv1x1_bwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
                      "adam_step_multi", "linear_fwd", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
-                     "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd")
+                     "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd",
+                     "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -96,8 +97,12 @@ def kernel_label(name, a):
         if a[9] is not None:
             return ("gemm_big_kernel" if dt == 1 and big_gemm(B, Fx, Fy, M) else "gemm_pf_kernel") + "(dW)"
         return "colsum_kernel"
-    if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd"):
+    if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
+    if name == "conv2d_grouped_fwd":
+        return "conv_gemm_kernel(fwd)"
+    if name == "conv2d_grouped_bwd":   # the GAN array asks for dX and dW in separate calls
+        return "conv_dx_kernel" if a[14] is not None else "conv_gemm_kernel(dW)+conv_splitk_reduce_kernel"
     if name == "conv1x1_bwd":          # called with either dX or dW requested, never both
         k = "gemm_pf_kernel" if a[5] == 1 else "gemm_kernel"
         return k + ("(dX)" if a[11] is not None else "(dW)+splitk_reduce_kernel")
@@ -121,6 +126,10 @@ def algorithmic_flops(name, a):
     if name in ("conv1x1_fwd", "conv1x1_bwd"):
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * Co * L
+    if name in ("conv2d_grouped_fwd", "conv2d_grouped_bwd"):
+        B, Nb, Ci, Co, H, W, kh, kw, st, pad = a[:10]
+        Ho, Wo = (H + 2 * pad - kh) // st + 1, (W + 2 * pad - kw) // st + 1
+        return 2.0 * B * Nb * Ho * Wo * Ci * Co * kh * kw
     return 0.0
 
 
@@ -156,6 +165,16 @@ def algorithmic_bytes(name, a):
         if a[9] is not None:
             return B * (M * Fx + M * Fy) * _es(dt) + B * Fx * Fy * 4
         return B * M * Fy * _es(dt)
+    if name in ("conv2d_grouped_fwd", "conv2d_grouped_bwd"):
+        B, Nb, Ci, Co, H, W, kh, kw, st, pad, dt = a[:11]
+        Ho, Wo = (H + 2 * pad - kh) // st + 1, (W + 2 * pad - kw) // st + 1
+        act_bytes = B * Nb * (Ci * H * W + Co * Ho * Wo) * _es(dt)
+        wbytes = B * Co * Ci * kh * kw
+        if name == "conv2d_grouped_bwd" and a[14] is None:
+            return act_bytes + wbytes * 4          # dW is fp32
+        return act_bytes + wbytes * _es(dt)
+    if name == "bias_act_nchw":
+        return 2 * a[0] * a[1] * a[2] * _es(a[3])
     if name == "act_fwd":
         return 2 * a[0] * _es(a[1])
     if name in ("act_bwd", "add"):
@@ -267,6 +286,16 @@ class Workload:
             self.config = {"workload": self.spec.name, "B": self.spec.B, "batch_per_model": self.spec.Nb,
                            "points": self.spec.L, "conv": list(self.spec.conv), "fc": list(self.spec.fc),
                            "step": "fwd+bwd+Adam"}
+        elif name == "c3":
+            from oracle import dcgan as oracle_model
+            self.spec = hi.spec_c3()
+            self.inp = hi.dcgan_inputs(self.spec)
+            self.cls = arrays.FusedDcgan
+            self.per_model_keys = ()
+            self.config = {"workload": self.spec.name, "B": self.spec.B, "images_per_model": self.spec.Nb,
+                           "image": "64x64x3", "generator": [l[:2] for l in self.spec.g_layers],
+                           "discriminator": [l[:2] for l in self.spec.d_layers],
+                           "step": "D step (real + fake) + G step, two Adam optimisers"}
         else:
             from oracle import mlp as oracle_model
             self.spec = hi.spec_c4()
@@ -288,7 +317,13 @@ class Workload:
             i1["drop_mask"] = None if self.inp["drop_mask"] is None else self.inp["drop_mask"][b:b + 1]
         for k in self.per_model_keys + ("lr", "beta1", "beta2", "eps", "wd"):
             i1[k] = self.inp[k][b:b + 1]
-        i1["params"] = self.inp["params"][b:b + 1]
+        if self.name == "c3":
+            cz = self.spec.g_layers[0][0]
+            i1["z"] = np.ascontiguousarray(self.inp["z"][:, cz * b:cz * (b + 1)])
+            i1["real"] = np.ascontiguousarray(self.inp["real"][:, 3 * b:3 * b + 3])
+            i1["gparams"], i1["dparams"] = self.inp["gparams"][b:b + 1], self.inp["dparams"][b:b + 1]
+        else:
+            i1["params"] = self.inp["params"][b:b + 1]
         return s1, i1
 
     def cpu_baseline(self):
@@ -299,15 +334,25 @@ class Workload:
             inp = hi.pointnet_cls_inputs(small)
             nsamp = small.Nb
             what = f"1 model x {small.Nb} clouds x {small.L} points"
+        elif self.name == "c3":
+            small = dataclasses.replace(self.spec, B=1, Nb=4)
+            inp = hi.dcgan_inputs(small)
+            nsamp = small.Nb
+            what = f"1 generator/discriminator pair x {small.Nb} images"
         else:
             seqs = 4
             small = dataclasses.replace(self.spec, B=1, R=seqs * (self.spec.R // self.spec.Nb), Nb=seqs)
             inp = hi.mlp_inputs(small)
             nsamp = seqs
             what = f"1 model x {seqs} sequences x {self.spec.R // self.spec.Nb} tokens, {small.blocks} blocks"
-        states = [self.oracle.init_state(inp["params"][0])]
-        t0 = time.perf_counter()
-        self.oracle.array_train_step(small, states, inp, 1)
+        if self.name == "c3":
+            gs, ds = [self.oracle.init_state(inp["gparams"][0])], [self.oracle.init_state(inp["dparams"][0])]
+            t0 = time.perf_counter()
+            self.oracle.array_train_iteration(small, gs, ds, inp, 1)
+        else:
+            states = [self.oracle.init_state(inp["params"][0])]
+            t0 = time.perf_counter()
+            self.oracle.array_train_step(small, states, inp, 1)
         dt = time.perf_counter() - t0
         try:
             from threadpoolctl import threadpool_info
@@ -324,7 +369,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c4"])
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c3", "c4"])
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--ops-report", default=None,

@@ -278,6 +278,11 @@ int hfta_softmax_xent(int B, int R, int K, int dtype, const void* logits, const 
                       float* loss, void* dlogits, void* stream);
 int hfta_bce_logits(int B, int64_t R, int dtype, const void* logits, const void* targets,
                     float* loss, void* dlogits, void* stream);
+/* The same for logits / targets / dlogits laid out by strides: element (b, r) at b*stride_b +
+ * r*stride_r (a discriminator's [Nb][B] output is stride_b = 1, stride_r = B). */
+int hfta_bce_logits_strided(int B, int64_t R, int dtype, const void* logits, const void* targets,
+                            float* loss, void* dlogits, int64_t stride_b, int64_t stride_r,
+                            void* stream);
 int hfta_mse(int B, int64_t R, int dtype, const void* pred, const void* target,
              float* loss, void* dpred, void* stream);
 

@@ -394,3 +394,221 @@ class FusedMlp(ParamArena):
             hb.add(B * R * E, dt, ds, dxl, d)          # d (this block's incoming gradient) is dead: reuse it
             P("add", a=ds, b=dxl, y=d)
         return self.loss
+
+
+class _Arena(ParamArena):
+    """A stand-alone parameter arena (one optimiser's worth of parameters)."""
+
+    def __init__(self, shapes, B, params, hp_inp, dtype, dev):
+        self.B = B
+        inp = dict(hp_inp)
+        inp["params"] = params
+        self._init_arena(shapes, B, inp, dtype, dev)
+        self.grad2 = torch.zeros_like(self.grad)      # second pass of a step that sums two passes
+
+    def g2(self, name):
+        return self._seg(self.grad2, name)
+
+
+class FusedDcgan:
+    """B generator/discriminator pairs trained as one job: every Conv2d / ConvTranspose2d is one
+    grouped implicit GEMM with groups = B, BatchNorm keeps per-model statistics, one Adam launch
+    per network updates all B models (per-model lr).  Activations are ``[Nb, B*C, H, W]``."""
+
+    BN_EPS = 1e-5
+    BN_MOMENTUM = 0.1
+    SLOPE = 0.2
+
+    def __init__(self, spec, inp: dict, device: str = "cuda"):
+        import hfta_inputs as hi
+        self.spec = spec
+        self.B, self.Nb = spec.B, spec.Nb
+        self.dt, self.tdt = _DT[spec.dtype], _TDT[spec.dtype]
+        self.dev = torch.device(device)
+        B, Nb = self.B, self.Nb
+        gsh, dsh = hi.dcgan_param_shapes(spec)
+        self.G = _Arena(gsh, B, inp["gparams"], inp, spec.dtype, self.dev)
+        self.D = _Arena(dsh, B, inp["dparams"], inp, spec.dtype, self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        act = dict(dtype=self.tdt, device=self.dev)
+        self.z = torch.from_numpy(inp["z"]).to(self.tdt).to(self.dev)
+        self.real = torch.from_numpy(inp["real"]).to(self.tdt).to(self.dev)
+        self.running, self.saved = {}, {}
+        for arena in (self.G, self.D):
+            for name, shp in arena.shapes:
+                if name.endswith(".bn.g"):
+                    k = name[:-2]
+                    self.running[k + ".rm"] = torch.zeros(B * shp[0], **f32)
+                    self.running[k + ".rv"] = torch.ones(B * shp[0], **f32)
+                    self.saved[k + ".mean"] = torch.empty(B * shp[0], **f32)
+                    self.saved[k + ".invstd"] = torch.empty(B * shp[0], **f32)
+        # generator activations: pre-BatchNorm and activated, per layer
+        self.g_pre, self.g_act = [], []
+        for (ci, co, hin, s, p) in spec.g_layers:
+            ho = (hin - 1) * s - 2 * p + 4
+            self.g_pre.append(torch.empty(Nb, B * co, ho, ho, **act))
+            self.g_act.append(torch.empty(Nb, B * co, ho, ho, **act))
+        self.g_act[-1] = self.g_pre[-1]                 # tanh runs in place on the last layer
+        self.fake = self.g_pre[-1]
+        self.d_pre, self.d_act = [], []
+        for (ci, co, hin, s, p) in spec.d_layers:
+            ho = (hin + 2 * p - 4) // s + 1
+            self.d_pre.append(torch.empty(Nb, B * co, ho, ho, **act))
+            self.d_act.append(torch.empty(Nb, B * co, ho, ho, **act))
+        self.d_act[0] = self.d_pre[0]                   # LeakyReLU in the first conv's epilogue
+        self.logits = self.d_pre[-1]
+        big = max(max(t.numel() for t in self.g_pre), max(t.numel() for t in self.d_pre), self.real.numel())
+        self.dbuf = [torch.empty(big, **act) for _ in range(2)]
+        self.ones = torch.ones(Nb, B, **act)
+        self.zeros = torch.zeros(Nb, B, **act)
+        self.dlogits = torch.empty(Nb, B, **act)
+        self.loss_d_real = torch.empty(B, **f32)
+        self.loss_d_fake = torch.empty(B, **f32)
+        self.loss_g = torch.empty(B, **f32)
+        ws = 4
+        for (ci, co, hin, s, p) in spec.d_layers:
+            ws = max(ws, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, ci, co, hin, hin, 4, 4, s, p, self.dt))
+        for (ci, co, hin, s, p) in spec.g_layers:
+            ho = (hin - 1) * s - 2 * p + 4
+            ws = max(ws, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, co, ci, ho, ho, 4, 4, s, p, self.dt))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+
+    # ------------------------------------------------------------------ generator
+    def g_forward(self):
+        B, Nb, dt, s = self.B, self.Nb, self.dt, self.spec
+        x = self.z
+        n = len(s.g_layers)
+        for i, (ci, co, hin, st, p) in enumerate(s.g_layers):
+            k = f"g{i}"
+            ho = (hin - 1) * st - 2 * p + 4
+            # ConvTranspose2d forward = the data-gradient form of the grouped convolution
+            hb.conv2d_grouped_bwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, None, self.G.w(k + ".w"), x,
+                                  self.g_pre[i], None, None, None)
+            if i < n - 1:
+                cs = _cs(B, co, ho * ho)
+                hb.bn_fwd(B, Nb, co, ho * ho, dt, self.g_pre[i], cs, self.G.master(k + ".bn.g"),
+                          self.G.master(k + ".bn.b"), self.BN_EPS, self.BN_MOMENTUM, self.running[k + ".bn.rm"],
+                          self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
+                          self.g_act[i], cs, hb.ACT_RELU)
+            else:
+                hb.bias_act_nchw(Nb, B * co, ho * ho, dt, self.g_pre[i], None, hb.ACT_TANH)
+            x = self.g_act[i]
+        return self.fake
+
+    def g_backward(self, dfake):
+        B, Nb, dt, s = self.B, self.Nb, self.dt, self.spec
+        n = len(s.g_layers)
+        d = dfake
+        for i in reversed(range(n)):
+            ci, co, hin, st, p = s.g_layers[i]
+            k = f"g{i}"
+            ho = (hin - 1) * st - 2 * p + 4
+            cnt = Nb * B * co * ho * ho
+            dpre = self._other(d)[:cnt]
+            if i == n - 1:
+                hb.act_bwd(cnt, dt, self.fake, d, dpre, hb.ACT_TANH, 0.0, 1)
+            else:
+                cs = _cs(B, co, ho * ho)
+                hb.bn_bwd(B, Nb, co, ho * ho, dt, self.g_pre[i], cs, d, cs, self.G.master(k + ".bn.g"),
+                          self.G.master(k + ".bn.b"), self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
+                          dpre, cs, self.G.g(k + ".bn.g"), self.G.g(k + ".bn.b"), hb.ACT_RELU, 0.0)
+            xin = self.z if i == 0 else self.g_act[i - 1]
+            # ConvTranspose2d weight gradient = the convolution's with input and output gradient exchanged
+            hb.conv2d_grouped_bwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, dpre, None, xin, None,
+                                  self.G.g(k + ".w"), None, self.ws)
+            if i > 0:
+                dx = self._other(dpre)[:Nb * B * ci * hin * hin]      # the incoming gradient's buffer: it is dead
+                # ConvTranspose2d data gradient = the convolution's forward
+                hb.conv2d_grouped_fwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, dpre, self.G.w(k + ".w"), None, dx)
+                d = dx
+
+    def _other(self, t):
+        """The ping-pong gradient buffer that `t` does not live in."""
+        return self.dbuf[1] if t.data_ptr() == self.dbuf[0].data_ptr() else self.dbuf[0]
+
+    # ------------------------------------------------------------------ discriminator
+    def d_forward(self, x):
+        B, Nb, dt, s = self.B, self.Nb, self.dt, self.spec
+        n = len(s.d_layers)
+        self._d_in = x
+        for i, (ci, co, hin, st, p) in enumerate(s.d_layers):
+            k = f"d{i}"
+            ho = (hin + 2 * p - 4) // st + 1
+            if i == 0:
+                hb.conv2d_grouped_fwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, x, self.D.w(k + ".w"), None,
+                                      self.d_pre[i], hb.ACT_LEAKY, self.SLOPE)
+            else:
+                hb.conv2d_grouped_fwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, x, self.D.w(k + ".w"), None,
+                                      self.d_pre[i])
+                if i < n - 1:
+                    cs = _cs(B, co, ho * ho)
+                    hb.bn_fwd(B, Nb, co, ho * ho, dt, self.d_pre[i], cs, self.D.master(k + ".bn.g"),
+                              self.D.master(k + ".bn.b"), self.BN_EPS, self.BN_MOMENTUM, self.running[k + ".bn.rm"],
+                              self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
+                              self.d_act[i], cs, hb.ACT_LEAKY, self.SLOPE)
+            x = self.d_act[i]
+        return self.logits
+
+    def d_backward(self, grad_of, want_dw=True, want_dx=False):
+        """Backward from ``self.dlogits``; ``grad_of(name)`` names where a parameter gradient goes."""
+        B, Nb, dt, s = self.B, self.Nb, self.dt, self.spec
+        n = len(s.d_layers)
+        d = self.dlogits
+        for i in reversed(range(n)):
+            ci, co, hin, st, p = s.d_layers[i]
+            k = f"d{i}"
+            ho = (hin + 2 * p - 4) // st + 1
+            cnt = Nb * B * co * ho * ho
+            if i == n - 1:
+                dpre = d
+            else:
+                dpre = self._other(d)[:cnt]
+                if i == 0:
+                    hb.act_bwd(cnt, dt, self.d_act[0], d, dpre, hb.ACT_LEAKY, self.SLOPE, 1)
+                else:
+                    cs = _cs(B, co, ho * ho)
+                    # without weight gradients the BatchNorm parameter gradients go to the spare buffer
+                    tgt = grad_of if want_dw else self.D.g2
+                    hb.bn_bwd(B, Nb, co, ho * ho, dt, self.d_pre[i], cs, d, cs, self.D.master(k + ".bn.g"),
+                              self.D.master(k + ".bn.b"), self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
+                              dpre, cs, tgt(k + ".bn.g"), tgt(k + ".bn.b"), hb.ACT_LEAKY, self.SLOPE)
+            xin = self._d_in if i == 0 else self.d_act[i - 1]
+            need_dx = i > 0 or want_dx
+            if want_dw:
+                hb.conv2d_grouped_bwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, xin, None, dpre, None,
+                                      grad_of(k + ".w"), None, self.ws)
+            if need_dx:
+                dx = self._other(dpre)[:Nb * B * ci * hin * hin]
+                hb.conv2d_grouped_bwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, None, self.D.w(k + ".w"), dpre, dx,
+                                      None, None, None)
+                d = dx
+        return d
+
+    def _bce(self, targets, loss):
+        hb.bce_logits_strided(self.B, self.Nb, self.dt, self.logits, targets, loss, self.dlogits, 1, self.B)
+
+    # ------------------------------------------------------------------ one iteration
+    def d_step(self):
+        """Discriminator step on BCE(D(real), 1) + BCE(D(fake), 0); `fake` must be current."""
+        self.d_forward(self.real)
+        self._bce(self.ones, self.loss_d_real)
+        self.d_backward(self.D.g)
+        self.d_forward(self.fake)
+        self._bce(self.zeros, self.loss_d_fake)
+        self.d_backward(self.D.g2)
+        hb.add(self.D.grad.numel(), hb.F32, self.D.grad, self.D.grad2, self.D.grad)
+
+    def g_step_backward(self):
+        """Generator loss BCE(D(fake), 1) through the current discriminator, back to G's parameters."""
+        self.d_forward(self.fake)
+        self._bce(self.ones, self.loss_g)
+        dfake = self.d_backward(None, want_dw=False, want_dx=True)
+        self.g_backward(dfake)
+
+    def train_step(self):
+        self.g_forward()
+        self.d_step()
+        self.D.adam()
+        self.g_step_backward()
+        self.G.adam()
+        return self.loss_g

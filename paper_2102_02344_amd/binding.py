@@ -68,6 +68,7 @@ _SIGS = {
     "hfta_layernorm_bwd": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_softmax_xent": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p]),
     "hfta_bce_logits": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p]),
+    "hfta_bce_logits_strided": (_i, [_i, _i64, _i, _p, _p, _p, _p, _i64, _i64, _p]),
     "hfta_mse": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p]),
 }
 for _name, (_res, _args) in _SIGS.items():
@@ -273,6 +274,11 @@ def softmax_xent(B, R, K, dtype, logits, labels, loss, dlogits, stream=None):
 def bce_logits(B, R, dtype, logits, targets, loss, dlogits, stream=None):
     _check(_lib.hfta_bce_logits(B, R, dtype, _ptr(logits), _ptr(targets), _ptr(loss), _ptr(dlogits),
                                 _stream(stream)), "hfta_bce_logits")
+
+
+def bce_logits_strided(B, R, dtype, logits, targets, loss, dlogits, stride_b, stride_r, stream=None):
+    _check(_lib.hfta_bce_logits_strided(B, R, dtype, _ptr(logits), _ptr(targets), _ptr(loss), _ptr(dlogits),
+                                        stride_b, stride_r, _stream(stream)), "hfta_bce_logits_strided")
 
 
 def mse(B, R, dtype, pred, target, loss, dpred, stream=None):

@@ -427,14 +427,16 @@ __global__ __launch_bounds__(1024) void softmax_xent_kernel(const T* __restrict_
 
 template <typename T, int KIND>  // KIND 0: BCE on sigmoid(logits); 1: MSE
 __global__ __launch_bounds__(1024) void pointwise_loss_kernel(const T* __restrict__ pred, const T* __restrict__ target,
-                                                             float* __restrict__ loss, T* __restrict__ dpred, int64_t R) {
+                                                             float* __restrict__ loss, T* __restrict__ dpred, int64_t R,
+                                                             int64_t sb, int64_t sr) {
   __shared__ float sh[16];
   const int b = blockIdx.x;
   float acc = 0.f;
   const float invR = 1.f / (float)R;
   for (int64_t i = threadIdx.x; i < R; i += blockDim.x) {
-    const float z = Elem<T>::load(pred + (int64_t)b * R + i);
-    const float t = Elem<T>::load(target + (int64_t)b * R + i);
+    const int64_t at = (int64_t)b * sb + i * sr;
+    const float z = Elem<T>::load(pred + at);
+    const float t = Elem<T>::load(target + at);
     float g;
     if (KIND == 0) {
       acc += fmaxf(z, 0.f) - z * t + log1pf(expf(-fabsf(z)));
@@ -444,7 +446,7 @@ __global__ __launch_bounds__(1024) void pointwise_loss_kernel(const T* __restric
       acc = fmaf(d, d, acc);
       g = 2.f * d;
     }
-    Elem<T>::store(dpred + (int64_t)b * R + i, g * invR);
+    Elem<T>::store(dpred + at, g * invR);
   }
   const float s = block_sum_1024(acc, sh);
   if (threadIdx.x == 0) loss[b] = s * invR;
@@ -686,26 +688,32 @@ int hfta_softmax_xent(int B, int R, int K, int dtype, const void* logits, const 
   return launch_status();
 }
 
-int hfta_bce_logits(int B, int64_t R, int dtype, const void* logits, const void* targets, float* loss, void* dlogits,
-                    void* stream) {
+int hfta_bce_logits_strided(int B, int64_t R, int dtype, const void* logits, const void* targets, float* loss,
+                            void* dlogits, int64_t stride_b, int64_t stride_r, void* stream) {
   if (B <= 0 || R <= 0 || !valid_dtype(dtype) || !logits || !targets || !loss || !dlogits) return HFTA_EINVAL;
+  if (stride_b <= 0 || stride_r <= 0) return HFTA_EINVAL;
   if (dtype == HFTA_BF16)
     hipLaunchKernelGGL((pointwise_loss_kernel<bf16_raw, 0>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
-                       (const bf16_raw*)logits, (const bf16_raw*)targets, loss, (bf16_raw*)dlogits, R);
+                       (const bf16_raw*)logits, (const bf16_raw*)targets, loss, (bf16_raw*)dlogits, R, stride_b, stride_r);
   else
     hipLaunchKernelGGL((pointwise_loss_kernel<float, 0>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
-                       (const float*)logits, (const float*)targets, loss, (float*)dlogits, R);
+                       (const float*)logits, (const float*)targets, loss, (float*)dlogits, R, stride_b, stride_r);
   return launch_status();
+}
+
+int hfta_bce_logits(int B, int64_t R, int dtype, const void* logits, const void* targets, float* loss, void* dlogits,
+                    void* stream) {
+  return hfta_bce_logits_strided(B, R, dtype, logits, targets, loss, dlogits, R, 1, stream);
 }
 
 int hfta_mse(int B, int64_t R, int dtype, const void* pred, const void* target, float* loss, void* dpred, void* stream) {
   if (B <= 0 || R <= 0 || !valid_dtype(dtype) || !pred || !target || !loss || !dpred) return HFTA_EINVAL;
   if (dtype == HFTA_BF16)
     hipLaunchKernelGGL((pointwise_loss_kernel<bf16_raw, 1>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
-                       (const bf16_raw*)pred, (const bf16_raw*)target, loss, (bf16_raw*)dpred, R);
+                       (const bf16_raw*)pred, (const bf16_raw*)target, loss, (bf16_raw*)dpred, R, R, (int64_t)1);
   else
     hipLaunchKernelGGL((pointwise_loss_kernel<float, 1>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
-                       (const float*)pred, (const float*)target, loss, (float*)dpred, R);
+                       (const float*)pred, (const float*)target, loss, (float*)dpred, R, R, (int64_t)1);
   return launch_status();
 }
 
