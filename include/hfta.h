@@ -125,15 +125,24 @@ int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
  *   ConvT bwd-data = hfta_conv2d_grouped_fwd; ConvT dW = hfta_conv2d_grouped_bwd's dW with the
  *              roles of X and dY exchanged the same way.
  * ---------------------------------------------------------------------- */
+/* workspace (optional, 256-byte aligned): with at least hfta_conv2d_grouped_fwd_workspace_bytes the
+ * convolution is lowered through a column buffer onto the batched GEMM kernels (sample index folded
+ * into the GEMM's columns); with NULL / less it runs as an implicit GEMM per (model, sample). */
+size_t hfta_conv2d_grouped_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W,
+                                               int kh, int kw, int stride, int pad, int dtype);
 int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
                             int stride, int pad, int dtype,
                             const void* X, const void* Wt, const void* bias, void* Y,
-                            int act, float act_slope, void* stream);
+                            int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
 
 /* dX:[Nb][B*Ci][H][W] storage dtype (NULL = skip); dW: fp32 [B*Co][Ci][kh][kw] (NULL = skip);
- * dbias: fp32 [B*Co] (NULL = skip). */
+ * dbias: fp32 [B*Co] (NULL = skip).  hfta_conv2d_grouped_bwd_workspace_bytes is the size that
+ * enables the column-buffer path; a smaller workspace (down to the implicit path's split-K
+ * partials, possibly none) selects the implicit GEMM kernels. */
 size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W,
                                                int kh, int kw, int stride, int pad, int dtype);
+size_t hfta_conv2d_grouped_bwd_min_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W,
+                                                   int kh, int kw, int stride, int pad, int dtype);
 int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
                             int stride, int pad, int dtype,
                             const void* X, const void* Wt, const void* dY,

@@ -63,6 +63,19 @@ class ParamArena:
                    for k in ("lr", "beta1", "beta2", "eps", "wd")}
         self.t = 0
 
+    def load_params(self, params) -> None:
+        """Overwrite the master weights (and their storage-dtype copy) with per-model values:
+        ``params[b][name]`` float32 arrays.  Optimiser moments are left as they are."""
+        host = np.empty(self.B * self.P, np.float32)
+        off = self.seg_offsets
+        for j, (name, shp) in enumerate(self.shapes):
+            n = off[j + 1] - off[j]
+            blk = np.stack([np.asarray(params[b][name], np.float32).reshape(-1) for b in range(self.B)])
+            host[self.B * off[j]:self.B * off[j] + self.B * n] = blk.reshape(-1)
+        self.theta.copy_(torch.from_numpy(host))
+        if self.lowp is not None:
+            self.lowp.copy_(self.theta)
+
     def _seg(self, buf: torch.Tensor, name: str) -> torch.Tensor:
         j = self._index[name]
         o, n = self.seg_offsets[j], self.seg_offsets[j + 1] - self.seg_offsets[j]
@@ -467,10 +480,13 @@ class FusedDcgan:
         self.loss_g = torch.empty(B, **f32)
         ws = 4
         for (ci, co, hin, s, p) in spec.d_layers:
-            ws = max(ws, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, ci, co, hin, hin, 4, 4, s, p, self.dt))
+            geo = (B, Nb, ci, co, hin, hin, 4, 4, s, p, self.dt)
+            ws = max(ws, hb.conv2d_grouped_bwd_workspace_bytes(*geo), hb.conv2d_grouped_fwd_workspace_bytes(*geo))
         for (ci, co, hin, s, p) in spec.g_layers:
             ho = (hin - 1) * s - 2 * p + 4
-            ws = max(ws, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, co, ci, ho, ho, 4, 4, s, p, self.dt))
+            geo = (B, Nb, co, ci, ho, ho, 4, 4, s, p, self.dt)
+            ws = max(ws, hb.conv2d_grouped_bwd_workspace_bytes(*geo), hb.conv2d_grouped_fwd_workspace_bytes(*geo))
+        # large enough for the column-buffer lowering of every layer (its sample-folded GEMMs)
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
 
     # ------------------------------------------------------------------ generator
@@ -483,7 +499,7 @@ class FusedDcgan:
             ho = (hin - 1) * st - 2 * p + 4
             # ConvTranspose2d forward = the data-gradient form of the grouped convolution
             hb.conv2d_grouped_bwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, None, self.G.w(k + ".w"), x,
-                                  self.g_pre[i], None, None, None)
+                                  self.g_pre[i], None, None, self.ws)
             if i < n - 1:
                 cs = _cs(B, co, ho * ho)
                 hb.bn_fwd(B, Nb, co, ho * ho, dt, self.g_pre[i], cs, self.G.master(k + ".bn.g"),
@@ -519,7 +535,8 @@ class FusedDcgan:
             if i > 0:
                 dx = self._other(dpre)[:Nb * B * ci * hin * hin]      # the incoming gradient's buffer: it is dead
                 # ConvTranspose2d data gradient = the convolution's forward
-                hb.conv2d_grouped_fwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, dpre, self.G.w(k + ".w"), None, dx)
+                hb.conv2d_grouped_fwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, dpre, self.G.w(k + ".w"), None, dx,
+                                      workspace=self.ws)
                 d = dx
 
     def _other(self, t):
@@ -536,10 +553,10 @@ class FusedDcgan:
             ho = (hin + 2 * p - 4) // st + 1
             if i == 0:
                 hb.conv2d_grouped_fwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, x, self.D.w(k + ".w"), None,
-                                      self.d_pre[i], hb.ACT_LEAKY, self.SLOPE)
+                                      self.d_pre[i], hb.ACT_LEAKY, self.SLOPE, workspace=self.ws)
             else:
                 hb.conv2d_grouped_fwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, x, self.D.w(k + ".w"), None,
-                                      self.d_pre[i])
+                                      self.d_pre[i], workspace=self.ws)
                 if i < n - 1:
                     cs = _cs(B, co, ho * ho)
                     hb.bn_fwd(B, Nb, co, ho * ho, dt, self.d_pre[i], cs, self.D.master(k + ".bn.g"),
@@ -580,7 +597,7 @@ class FusedDcgan:
             if need_dx:
                 dx = self._other(dpre)[:Nb * B * ci * hin * hin]
                 hb.conv2d_grouped_bwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, None, self.D.w(k + ".w"), dpre, dx,
-                                      None, None, None)
+                                      None, None, self.ws)
                 d = dx
         return d
 

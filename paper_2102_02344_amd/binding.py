@@ -47,7 +47,9 @@ _SIGS = {
     "hfta_conv1x1_fwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _s4, _i, _f, _p]),
     "hfta_conv1x1_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _p, _p, _p, _sz, _p]),
-    "hfta_conv2d_grouped_fwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _i, _f, _p]),
+    "hfta_conv2d_grouped_fwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _i, _f, _p, _sz, _p]),
+    "hfta_conv2d_grouped_fwd_workspace_bytes": (_sz, [_i] * 11),
+    "hfta_conv2d_grouped_bwd_min_workspace_bytes": (_sz, [_i] * 11),
     "hfta_conv2d_grouped_bwd_workspace_bytes": (_sz, [_i] * 11),
     "hfta_conv2d_grouped_bwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_bn_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
@@ -154,11 +156,20 @@ def conv1x1_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, dY, dys, dX, dxs, dW, dbias, 
            "hfta_conv1x1_bwd")
 
 
+def conv2d_grouped_fwd_workspace_bytes(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype) -> int:
+    return _lib.hfta_conv2d_grouped_fwd_workspace_bytes(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype)
+
+
 def conv2d_grouped_fwd(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype, X, Wt, bias, Y, act=ACT_NONE,
-                       act_slope=0.0, stream=None):
+                       act_slope=0.0, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
     _check(_lib.hfta_conv2d_grouped_fwd(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype, _ptr(X), _ptr(Wt),
-                                        _ptr(bias), _ptr(Y), act, act_slope, _stream(stream)),
+                                        _ptr(bias), _ptr(Y), act, act_slope, wp, wb, _stream(stream)),
            "hfta_conv2d_grouped_fwd")
+
+
+def conv2d_grouped_bwd_min_workspace_bytes(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype) -> int:
+    return _lib.hfta_conv2d_grouped_bwd_min_workspace_bytes(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype)
 
 
 def conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, W_, kh, kw, stride, pad, dtype) -> int:

@@ -397,6 +397,215 @@ __global__ __launch_bounds__(256) void conv_dbias_kernel(const T* __restrict__ d
   if (threadIdx.x == 0) out[k] = (part[0] + part[1]) + (part[2] + part[3]);
 }
 
+// ---- lowering through a column buffer ------------------------------------------
+// With a caller-supplied workspace the convolution becomes one large GEMM per model on the
+// batched GEMM kernels: the sample index is folded into the GEMM's column dimension
+// (N = Nb * Ho * Wo), so small images fill the tiles, and the operands are plain matrices.
+//   col[b][k = (c, ky, kx)][n * Ho*Wo + pix]          (im2col_kernel)
+//   forward   Y[b]    = W[b] (Co x K)  * col[b]        -> written straight into [Nb][B*Co][Ho*Wo]
+//   weights   dW[b]   = dYp[b] (Co x N) * col[b]^T
+//   data      dcol[b] = W[b]^T * dYp[b] (fp32),  dX = col2im(dcol)   (col2im_kernel: a gather, no atomics;
+//             the per-tap partial sums stay fp32 so dX is rounded to the storage type once)
+// dYp[b][co][n * Ho*Wo + pix] is the output gradient repacked model- and channel-major.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void im2col_kernel(const T* __restrict__ X, T* __restrict__ col, int B, int Nb, int Ci,
+                                                    int H, int W, int Ho, int Wo, int kh, int kw, int stride, int pad,
+                                                    FastDiv d_khkw, FastDiv d_kw, FastDiv d_wov, FastDiv d_rows) {
+  // one thread per V consecutive output pixels of a row; grid.y = k, grid.z = b
+  const int K = Ci * kh * kw;
+  const int b = blockIdx.z, k = blockIdx.y;
+  int c, r, ky, kx;
+  d_khkw.divmod(k, c, r);
+  d_kw.divmod(r, ky, kx);
+  const int wov = Wo / V;                                  // vectors per output row
+  const int64_t N = (int64_t)Nb * Ho * Wo;
+  T* dst = col + ((int64_t)b * K + k) * N;
+  const int total = Nb * Ho * wov;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+    int row, xv, n, y;
+    d_wov.divmod(i, row, xv);
+    d_rows.divmod(row, n, y);
+    const int iy = y * stride + ky - pad;
+    const T* src = X + (((int64_t)n * B + b) * Ci + c) * H * W + (int64_t)iy * W;
+    T v[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      const int ix = (xv * V + e) * stride + kx - pad;
+      v[e] = ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) ? src[ix] : T(0);
+    }
+    T* o = dst + ((int64_t)n * Ho + y) * Wo + xv * V;
+    if (V * sizeof(T) == 16) *reinterpret_cast<uint4*>(o) = *reinterpret_cast<const uint4*>(v);
+    else if (V * sizeof(T) == 8) *reinterpret_cast<uint2*>(o) = *reinterpret_cast<const uint2*>(v);
+    else {
+#pragma unroll
+      for (int e = 0; e < V; ++e) o[e] = v[e];
+    }
+  }
+}
+
+// dYp[b][co][n*HoWo + pix] = dY[n][b*Co + co][pix]
+template <typename T>
+__global__ __launch_bounds__(256) void pack_dy_kernel(const T* __restrict__ dY, T* __restrict__ dYp, int B, int Nb, int Co,
+                                                     int HoWo, int vec) {
+  const int bc = blockIdx.z * Co + blockIdx.y;             // b * Co + co
+  const int64_t N = (int64_t)Nb * HoWo;
+  constexpr int LV = 16 / (int)sizeof(T);
+  if (vec) {                                               // aligned, and whole 16-byte pieces stay inside one sample
+    const int64_t nv = N / LV;
+    const int vps = HoWo / LV;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (int64_t)gridDim.x * 256) {
+      const int n = (int)(i / vps), pv = (int)(i - (int64_t)n * vps);
+      reinterpret_cast<uint4*>(dYp + (int64_t)bc * N)[i] =
+          reinterpret_cast<const uint4*>(dY + ((int64_t)n * B * Co + bc) * HoWo)[pv];
+    }
+    return;
+  }
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 256) {
+    const int n = (int)(i / HoWo), pix = (int)(i - (int64_t)n * HoWo);
+    dYp[(int64_t)bc * N + i] = dY[((int64_t)n * B * Co + bc) * HoWo + pix];
+  }
+}
+
+// dX[n][b*Ci + c][iy][ix] = sum over the taps that reach (iy, ix) of dcol[b][(c, ky, kx)][n, y, x]
+template <typename T>
+__global__ __launch_bounds__(256) void col2im_kernel(const float* __restrict__ dcol, T* __restrict__ dX, int B, int Nb, int Ci,
+                                                    int H, int W, int Ho, int Wo, int kh, int kw, int stride, int pad) {
+  const int b = blockIdx.z, c = blockIdx.y;
+  const int bc = b * Ci + c;
+  const int64_t N = (int64_t)Nb * Ho * Wo;
+  const int K = Ci * kh * kw;
+  const float* src = dcol + ((int64_t)b * K + (int64_t)c * kh * kw) * N;
+  const int64_t total = (int64_t)Nb * H * W;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int n = (int)(i / (H * W));
+    const int r = (int)(i - (int64_t)n * H * W);
+    const int iy = r / W, ix = r - iy * W;
+    float s = 0.f;
+    for (int ky = 0; ky < kh; ++ky) {
+      const int ty = iy + pad - ky;
+      if (ty < 0 || ty % stride != 0) continue;
+      const int y = ty / stride;
+      if (y >= Ho) continue;
+      for (int kx = 0; kx < kw; ++kx) {
+        const int tx = ix + pad - kx;
+        if (tx < 0 || tx % stride != 0) continue;
+        const int x = tx / stride;
+        if (x >= Wo) continue;
+        s += src[(int64_t)(ky * kw + kx) * N + ((int64_t)n * Ho + y) * Wo + x];
+      }
+    }
+    Elem<T>::store(dX + ((int64_t)n * B * Ci + bc) * H * W + r, s);
+  }
+}
+
+// LDS-staged forms of the two lowering kernels: a block owns one channel of one model for NI
+// samples, so the image (im2col) or the kh*kw column-buffer rows (col2im) are read from memory
+// once, in whole contiguous runs, and the kh*kw-fold reuse happens in LDS.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void im2col_lds_kernel(const T* __restrict__ X, T* __restrict__ col, int B, int Nb, int Ci,
+                                                        int H, int W, int Ho, int Wo, int kh, int kw, int stride, int pad,
+                                                        int NI, int vec_in, FastDiv d_howo, FastDiv d_wo) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char conv_dyn_smem[];
+  T* img = reinterpret_cast<T*>(conv_dyn_smem);             // [NI][H*W]
+  const int b = blockIdx.z, c = blockIdx.y, n0 = blockIdx.x * NI;
+  const int ni = min(NI, Nb - n0);
+  const int HW = H * W, HoWo = Ho * Wo, taps = kh * kw;
+  const int64_t N = (int64_t)Nb * HoWo;
+  constexpr int LV = 16 / (int)sizeof(T);
+  if (vec_in) {                                             // 16-byte aligned images of whole 16-byte pieces
+    const int vpi = HW / LV;
+    for (int i = threadIdx.x; i < ni * vpi; i += 256) {
+      const int n = i / vpi, r = i - n * vpi;
+      reinterpret_cast<uint4*>(img)[i] =
+          reinterpret_cast<const uint4*>(X + (((int64_t)(n0 + n) * B + b) * Ci + c) * HW)[r];
+    }
+  } else {
+    for (int i = threadIdx.x; i < ni * HW; i += 256) {
+      const int n = i / HW, r = i - n * HW;
+      img[i] = X[(((int64_t)(n0 + n) * B + b) * Ci + c) * HW + r];
+    }
+  }
+  __syncthreads();
+  const int cnt = ni * HoWo;                                // a multiple of V (host)
+  for (int tap = 0; tap < taps; ++tap) {
+    const int ky = tap / kw, kx = tap - ky * kw;
+    T* dst = col + ((int64_t)b * Ci * taps + (int64_t)c * taps + tap) * N + (int64_t)n0 * HoWo;
+    for (int i = threadIdx.x * V; i < cnt; i += 256 * V) {
+      T v[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        int n, p, y, x;
+        d_howo.divmod(i + e, n, p);
+        d_wo.divmod(p, y, x);
+        const int iy = y * stride + ky - pad, ix = x * stride + kx - pad;
+        v[e] = ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) ? img[n * HW + iy * W + ix] : T(0);
+      }
+      if (V * sizeof(T) == 16) *reinterpret_cast<uint4*>(dst + i) = *reinterpret_cast<const uint4*>(v);
+      else if (V * sizeof(T) == 8) *reinterpret_cast<uint2*>(dst + i) = *reinterpret_cast<const uint2*>(v);
+      else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) dst[i + e] = v[e];
+      }
+    }
+  }
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(256) void col2im_lds_kernel(const float* __restrict__ dcol, T* __restrict__ dX, int B, int Nb, int Ci,
+                                                        int H, int W, int Ho, int Wo, int kh, int kw, int stride, int pad,
+                                                        int NI, FastDiv d_hw, FastDiv d_w, FastDiv d_s) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char conv_dyn_smem[];
+  float* rows = reinterpret_cast<float*>(conv_dyn_smem);    // [kh*kw][NI*Ho*Wo], fp32 partial sums
+  const int b = blockIdx.z, c = blockIdx.y, n0 = blockIdx.x * NI;
+  const int ni = min(NI, Nb - n0);
+  const int HW = H * W, HoWo = Ho * Wo, taps = kh * kw;
+  const int64_t N = (int64_t)Nb * HoWo;
+  const int seg = NI * HoWo, cnt = ni * HoWo;
+  constexpr int LV = 4;
+  for (int tap = 0; tap < taps; ++tap) {
+    const float* src = dcol + ((int64_t)b * Ci * taps + (int64_t)c * taps + tap) * N + (int64_t)n0 * HoWo;
+    if (HoWo % LV == 0) {
+      for (int i = threadIdx.x; i < cnt / LV; i += 256)
+        reinterpret_cast<uint4*>(rows + tap * seg)[i] = reinterpret_cast<const uint4*>(src)[i];
+    } else {
+      for (int i = threadIdx.x; i < cnt; i += 256) rows[tap * seg + i] = src[i];
+    }
+  }
+  __syncthreads();
+  const int out = ni * HW;                                  // a multiple of V (host)
+  T* dst = dX + (((int64_t)n0 * B + b) * Ci + c) * HW;      // sample n at + n * B*Ci*HW
+  for (int i = threadIdx.x * V; i < out; i += 256 * V) {
+    T v[V];
+    int n0e = 0, r0 = 0;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      int n, r, iy, ix;
+      d_hw.divmod(i + e, n, r);
+      d_w.divmod(r, iy, ix);
+      if (e == 0) { n0e = n; r0 = r; }
+      float sum = 0.f;
+      int qy, ry, qx, rx;
+      d_s.divmod(iy + pad, qy, ry);                         // taps ky = ry, ry + s, ...: y = qy, qy - 1, ...
+      d_s.divmod(ix + pad, qx, rx);
+      for (int ky = ry, y = qy; ky < kh; ky += stride, --y) {
+        if ((unsigned)y >= (unsigned)Ho) continue;
+        for (int kx = rx, x = qx; kx < kw; kx += stride, --x) {
+          if ((unsigned)x >= (unsigned)Wo) continue;
+          sum += rows[(ky * kw + kx) * seg + n * HoWo + y * Wo + x];
+        }
+      }
+      v[e] = Elem<T>::from_f32(sum);
+    }
+    T* d = dst + (int64_t)n0e * B * Ci * HW + r0;           // V | H*W: the V elements share a sample
+    if (V * sizeof(T) == 16) *reinterpret_cast<uint4*>(d) = *reinterpret_cast<const uint4*>(v);
+    else if (V * sizeof(T) == 8) *reinterpret_cast<uint2*>(d) = *reinterpret_cast<const uint2*>(v);
+    else {
+#pragma unroll
+      for (int e = 0; e < V; ++e) d[e] = v[e];
+    }
+  }
+}
+
 struct ConvGeom { int Ho, Wo; };
 
 int check_conv(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype, ConvGeom* g) {
@@ -456,17 +665,157 @@ int launch_conv(ConvArgs a, int dtype, unsigned gz, hipStream_t st) {
   return launch_status();
 }
 
+
+// ---- host side of the lowered path ---------------------------------------------
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Lowered {
+  int64_t K, N, HoWo;
+  size_t col_bytes, dcol_bytes, dyp_bytes, part_bytes;   // dcol: fp32 per-tap partial sums of the data gradient
+};
+
+GemmDesc lowered_dw_desc(int B, int Co, const Lowered& L, int dtype) {
+  GemmDesc d{};
+  d.S = 1; d.G0 = B; d.G1 = 1;
+  d.M = Co; d.N = (int)L.K; d.K = (int)L.N;
+  d.a_kc = true; d.a_ld = L.N; d.a_g0 = (int64_t)Co * L.N;
+  d.b_kc = true; d.b_ld = L.N; d.b_g0 = L.K * L.N;
+  d.c_ld = L.K; d.c_g0 = (int64_t)Co * L.K;
+  d.act = HFTA_ACT_NONE; d.dtype = dtype; d.out_f32 = true; d.splits = 1;
+  return d;
+}
+
+bool lowered_sizes(int B, int Nb, int Ci, int Co, ConvGeom g, int kh, int kw, int dtype, Lowered* L) {
+  L->K = (int64_t)Ci * kh * kw;
+  L->HoWo = (int64_t)g.Ho * g.Wo;
+  L->N = (int64_t)Nb * L->HoWo;
+  if (L->N > 0x7fffffffLL || L->K > 0x7fffffffLL || L->K * L->N > ((int64_t)1 << 40) || B > 65535 || L->K > 65535 ||
+      Co > 65535 || Ci > 65535)
+    return false;
+  const size_t es = dtype_size(dtype);
+  L->col_bytes = align256((size_t)B * L->K * L->N * es);
+  L->dcol_bytes = align256((size_t)B * L->K * L->N * sizeof(float));
+  L->dyp_bytes = align256((size_t)B * Co * L->N * es);
+  GemmDesc d = lowered_dw_desc(B, Co, *L, dtype);
+  L->part_bytes = align256(gemm_partial_bytes(d, gemm_pick_splits(d)));
+  return true;
+}
+
+unsigned row_blocks(int64_t items) {
+  int64_t b = (items + 255) / 256;
+  return (unsigned)(b > 64 ? 64 : (b < 1 ? 1 : b));
+}
+
+constexpr size_t CONV_LDS_BUDGET = 48 * 1024;
+
+// samples per block: enough output pixels to keep 256 threads busy, within the LDS budget
+static int pick_ni(int Nb, int per_sample_out, size_t per_sample_lds) {
+  int ni = (2048 + per_sample_out - 1) / per_sample_out;
+  if (ni > Nb) ni = Nb;
+  while (ni > 1 && (size_t)ni * per_sample_lds > CONV_LDS_BUDGET) --ni;
+  return ni < 1 ? 1 : ni;
+}
+
+template <typename T>
+int launch_im2col_t(const void* X, void* col, int B, int Nb, int Ci, int H, int W, ConvGeom g, int kh, int kw, int stride,
+                    int pad, hipStream_t st) {
+  const int K = Ci * kh * kw;
+  const T* x = (const T*)X;
+  T* cb = (T*)col;
+  const size_t img_bytes = (size_t)H * W * sizeof(T);
+  if (img_bytes <= CONV_LDS_BUDGET && Ci <= 65535) {
+    const int HoWo = g.Ho * g.Wo;
+    const int ni = pick_ni(Nb, HoWo, img_bytes);
+    int V = 16 / (int)sizeof(T);
+    while (V > 1 && HoWo % V != 0) V >>= 1;
+    const dim3 gr((unsigned)((Nb + ni - 1) / ni), (unsigned)Ci, (unsigned)B);
+    const size_t lds = (size_t)ni * img_bytes;
+    const FastDiv dh = FastDiv::make(HoWo), dw = FastDiv::make(g.Wo);
+    const int vec_in = (H * W) % (16 / (int)sizeof(T)) == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0;
+#define HFTA_IM2COL_L(VV) hipLaunchKernelGGL((im2col_lds_kernel<T, VV>), gr, dim3(256), lds, st, x, cb, B, Nb, Ci, H, W, g.Ho, g.Wo, kh, kw, stride, pad, ni, vec_in, dh, dw)
+    if (V == 8) HFTA_IM2COL_L(8); else if (V == 4) HFTA_IM2COL_L(4); else if (V == 2) HFTA_IM2COL_L(2); else HFTA_IM2COL_L(1);
+#undef HFTA_IM2COL_L
+    return launch_status();
+  }
+  int V = 16 / (int)sizeof(T);
+  while (V > 1 && g.Wo % V != 0) V >>= 1;
+  const dim3 gr(row_blocks((int64_t)Nb * g.Ho * (g.Wo / V)), (unsigned)K, (unsigned)B);
+  const FastDiv a = FastDiv::make(kh * kw), b2 = FastDiv::make(kw), c = FastDiv::make(g.Wo / V), d = FastDiv::make(g.Ho);
+#define HFTA_IM2COL(VV) hipLaunchKernelGGL((im2col_kernel<T, VV>), gr, dim3(256), 0, st, x, cb, B, Nb, Ci, H, W, g.Ho, g.Wo, kh, kw, stride, pad, a, b2, c, d)
+  if (V == 8) HFTA_IM2COL(8); else if (V == 4) HFTA_IM2COL(4); else if (V == 2) HFTA_IM2COL(2); else HFTA_IM2COL(1);
+#undef HFTA_IM2COL
+  return launch_status();
+}
+
+template <typename T>
+int launch_col2im_t(const void* dcol, void* dX, int B, int Nb, int Ci, int H, int W, ConvGeom g, int kh, int kw, int stride,
+                    int pad, hipStream_t st) {
+  const int HoWo = g.Ho * g.Wo, HW = H * W;
+  const size_t per_sample = (size_t)kh * kw * HoWo * sizeof(float);
+  if (per_sample <= CONV_LDS_BUDGET) {
+    const int ni = pick_ni(Nb, HW, per_sample);
+    int V = 16 / (int)sizeof(T);
+    while (V > 1 && (HW % V != 0 || reinterpret_cast<uintptr_t>(dX) % (V * sizeof(T)) != 0)) V >>= 1;
+    const dim3 gr((unsigned)((Nb + ni - 1) / ni), (unsigned)Ci, (unsigned)B);
+    const size_t lds = (size_t)ni * per_sample;
+    const FastDiv dhw = FastDiv::make(HW), dw = FastDiv::make(W), ds = FastDiv::make(stride);
+#define HFTA_COL2IM_L(VV) hipLaunchKernelGGL((col2im_lds_kernel<T, VV>), gr, dim3(256), lds, st, (const float*)dcol, (T*)dX, B, Nb, Ci, H, W, g.Ho, g.Wo, kh, kw, stride, pad, ni, dhw, dw, ds)
+    if (V == 8) HFTA_COL2IM_L(8); else if (V == 4) HFTA_COL2IM_L(4); else if (V == 2) HFTA_COL2IM_L(2); else HFTA_COL2IM_L(1);
+#undef HFTA_COL2IM_L
+    return launch_status();
+  }
+  const dim3 cgrid(row_blocks((int64_t)Nb * HW), (unsigned)Ci, (unsigned)B);
+  hipLaunchKernelGGL(col2im_kernel<T>, cgrid, dim3(256), 0, st, (const float*)dcol, (T*)dX, B, Nb, Ci, H, W, g.Ho, g.Wo, kh, kw,
+                     stride, pad);
+  return launch_status();
+}
+
+int lowered_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype, ConvGeom g,
+                const Lowered& L, const void* X, const void* Wt, const void* bias, void* Y, int act, float slope,
+                void* ws, hipStream_t st) {
+  int rc = dtype == HFTA_BF16 ? launch_im2col_t<bf16_raw>(X, ws, B, Nb, Ci, H, W, g, kh, kw, stride, pad, st)
+                              : launch_im2col_t<float>(X, ws, B, Nb, Ci, H, W, g, kh, kw, stride, pad, st);
+  if (rc != HFTA_OK) return rc;
+  GemmDesc d{};
+  d.S = 1; d.G0 = B; d.G1 = 1;
+  d.A = Wt; d.Bm = ws; d.C = Y;
+  d.M = Co; d.N = (int)L.N; d.K = (int)L.K;
+  d.a_kc = true; d.a_ld = L.K; d.a_g0 = (int64_t)Co * L.K;
+  d.b_kc = false; d.b_ld = L.N; d.b_g0 = L.K * L.N;
+  d.c_ld = L.HoWo; d.c_g0 = (int64_t)Co * L.HoWo;
+  d.c_seg = (int)L.HoWo; d.c_seg_stride = (int64_t)B * Co * L.HoWo;
+  d.bias = bias; d.bias_mode = 1; d.bias_g0 = Co;
+  d.act = act; d.slope = slope; d.dtype = dtype; d.out_f32 = false; d.splits = 1;
+  return gemm_launch(d, st);
+}
+
 }  // namespace
 
 extern "C" {
 
+size_t hfta_conv2d_grouped_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride,
+                                               int pad, int dtype) {
+  ConvGeom g;
+  Lowered L;
+  if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
+  if (!lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L)) return 0;
+  return L.col_bytes;
+}
+
 int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype,
                             const void* X, const void* Wt, const void* bias, void* Y, int act, float act_slope,
-                            void* stream) {
+                            void* workspace, size_t ws_bytes, void* stream) {
   ConvGeom g;
   int rc = check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g);
   if (rc != HFTA_OK) return rc;
   if (!X || !Wt || !Y || !valid_act(act)) return HFTA_EINVAL;
+  Lowered L;
+  if (workspace && reinterpret_cast<uintptr_t>(workspace) % 256 == 0 &&
+      lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L) && ws_bytes >= L.col_bytes) {
+    rc = lowered_fwd(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, g, L, X, Wt, bias, Y, act, act_slope, workspace,
+                     as_stream(stream));
+    if (rc != HFTA_EUNSUPPORTED) return rc;
+  }
   ConvArgs a = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
   a.X = X; a.Wt = Wt; a.Out = Y; a.bias = bias; a.act = act; a.slope = act_slope;
   a.a_vec = reinterpret_cast<uintptr_t>(Wt) % 16 == 0;
@@ -475,15 +824,34 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   return launch_conv<CONV_FWD>(a, dtype, (unsigned)(B * Nb), as_stream(stream));
 }
 
-size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride,
-                                               int pad, int dtype) {
-  ConvGeom g;
-  if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
+static size_t implicit_bwd_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad,
+                                 int dtype, ConvGeom g) {
   ConvArgs a = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
   a.M = Co; a.N = Ci * kh * kw; a.K = g.Ho * g.Wo; a.S = Nb;
   finish_tiles(a, dtype);
   const int sp = dw_splits(a);
   return sp > 1 ? (size_t)sp * B * (size_t)a.M * a.N * sizeof(float) : 0;
+}
+
+/* What the implicit-GEMM path needs (the weight gradient's split partials; may be 0). */
+size_t hfta_conv2d_grouped_bwd_min_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
+                                                   int stride, int pad, int dtype) {
+  ConvGeom g;
+  if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
+  return implicit_bwd_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, g);
+}
+
+/* The size that enables the column-buffer path; anything from the implicit path's own need (the
+ * split partials of the weight gradient, possibly 0) upwards is accepted and selects that path. */
+size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride,
+                                               int pad, int dtype) {
+  ConvGeom g;
+  if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
+  const size_t imp = implicit_bwd_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, g);
+  Lowered L;
+  if (!lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L)) return imp;
+  const size_t low = L.dcol_bytes + L.dyp_bytes + L.part_bytes;
+  return low > imp ? low : imp;
 }
 
 int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype,
@@ -494,6 +862,59 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   if (rc != HFTA_OK) return rc;
   if (!dY || (dX && !Wt) || (dW && !X)) return HFTA_EINVAL;
   hipStream_t st = as_stream(stream);
+  Lowered L;
+  if ((dX || dW) && workspace && reinterpret_cast<uintptr_t>(workspace) % 256 == 0 &&
+      lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L) && ws_bytes >= L.dcol_bytes + L.dyp_bytes + L.part_bytes) {
+    unsigned char* wsb = reinterpret_cast<unsigned char*>(workspace);
+    void* colb = wsb;
+    void* dyp = wsb + L.dcol_bytes;
+    float* part = reinterpret_cast<float*>(wsb + L.dcol_bytes + L.dyp_bytes);
+    const dim3 pgrid(row_blocks(L.N), (unsigned)Co, (unsigned)B);
+    const int pvec = L.HoWo % (16 / (int64_t)dtype_size(dtype)) == 0 && reinterpret_cast<uintptr_t>(dY) % 16 == 0;
+    if (dtype == HFTA_BF16)
+      hipLaunchKernelGGL(pack_dy_kernel<bf16_raw>, pgrid, dim3(256), 0, st, (const bf16_raw*)dY, (bf16_raw*)dyp, B, Nb, Co,
+                         (int)L.HoWo, pvec);
+    else
+      hipLaunchKernelGGL(pack_dy_kernel<float>, pgrid, dim3(256), 0, st, (const float*)dY, (float*)dyp, B, Nb, Co,
+                         (int)L.HoWo, pvec);
+    if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+    if (dW) {
+      rc = dtype == HFTA_BF16 ? launch_im2col_t<bf16_raw>(X, colb, B, Nb, Ci, H, W, g, kh, kw, stride, pad, st)
+                              : launch_im2col_t<float>(X, colb, B, Nb, Ci, H, W, g, kh, kw, stride, pad, st);
+      if (rc != HFTA_OK) return rc;
+      GemmDesc d = lowered_dw_desc(B, Co, L, dtype);
+      d.A = dyp; d.Bm = colb; d.C = dW;
+      d.splits = gemm_pick_splits(d);
+      d.partial = part;
+      rc = gemm_launch(d, st);
+      if (rc != HFTA_OK) return rc;
+    }
+    if (dX) {
+      GemmDesc d{};
+      d.S = 1; d.G0 = B; d.G1 = 1;
+      d.A = Wt; d.Bm = dyp; d.C = colb;
+      d.M = (int)L.K; d.N = (int)L.N; d.K = Co;
+      d.a_kc = false; d.a_ld = L.K; d.a_g0 = (int64_t)Co * L.K;      // A[m = k][kk = co] = W[co][k]
+      d.b_kc = false; d.b_ld = L.N; d.b_g0 = (int64_t)Co * L.N;
+      d.c_ld = L.N; d.c_g0 = L.K * L.N;
+      d.act = HFTA_ACT_NONE; d.dtype = dtype; d.out_f32 = true; d.splits = 1;   // fp32 partial sums per tap
+      rc = gemm_launch(d, st);
+      if (rc != HFTA_OK) return rc;
+      rc = dtype == HFTA_BF16 ? launch_col2im_t<bf16_raw>(colb, dX, B, Nb, Ci, H, W, g, kh, kw, stride, pad, st)
+                              : launch_col2im_t<float>(colb, dX, B, Nb, Ci, H, W, g, kh, kw, stride, pad, st);
+      if (rc != HFTA_OK) return rc;
+    }
+    if (dbias) {
+      if (dtype == HFTA_BF16)
+        hipLaunchKernelGGL(conv_dbias_kernel<bf16_raw>, dim3((unsigned)(B * Co)), dim3(256), 0, st, (const bf16_raw*)dY,
+                           dbias, Nb, B * Co, L.HoWo);
+      else
+        hipLaunchKernelGGL(conv_dbias_kernel<float>, dim3((unsigned)(B * Co)), dim3(256), 0, st, (const float*)dY, dbias, Nb,
+                           B * Co, L.HoWo);
+      return launch_status();
+    }
+    return HFTA_OK;
+  }
   ConvArgs w = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
   if (dW) {
     w.X = X; w.dY = dY; w.Out = dW;

@@ -45,6 +45,10 @@ struct GemmDesc {
   bool out_f32;
   int splits;                      // > 1: fp32 partials [split][G0*G1][M][N] go to `partial`
   float* partial;
+  // C's columns in segments of c_seg (0 = one contiguous row): column n lives at
+  // (n / c_seg) * c_seg_stride + n % c_seg past the row start (an [N][C][HW] image tensor seen as [C][N*HW])
+  int c_seg;
+  int64_t c_seg_stride;
 };
 
 struct GemmArgs {
@@ -63,6 +67,8 @@ struct GemmArgs {
   int bias_mode, act;
   float slope;
   uint32_t a_extent, b_extent;   // bytes from an operand slice's first to one past its last element
+  int c_seg;
+  int64_t c_seg_stride;
 };
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -306,9 +312,15 @@ __device__ __forceinline__ void stage_acc(f32x16_t (&acc)[2][2], unsigned char* 
 // Phase 2: staged rows -> global memory.  VB = bytes per lane (16, 8: whole aligned pieces of a
 // row, consecutive lanes on consecutive pieces so a wavefront's store covers whole row segments;
 // 0: single elements).  INTERIOR: the tile lies wholly inside the matrix, no per-lane checks.
+__device__ __forceinline__ int64_t col_offset(int n, int c_seg, int64_t c_seg_stride) {
+  if (c_seg <= 0) return n;
+  const int q = n / c_seg;
+  return (int64_t)q * c_seg_stride + (n - q * c_seg);
+}
+
 template <typename OutT, int VB, bool INTERIOR>
 __device__ __forceinline__ void store_rows(const unsigned char* lds, OutT* Cb, int64_t c_ld, int M, int N,
-                                           int mbase, int n0, int t) {
+                                           int mbase, int n0, int t, int c_seg, int64_t c_seg_stride) {
   constexpr int ES = sizeof(OutT);
   constexpr int RP = ES == 2 ? 128 : 64;
   constexpr int PITCH = ES == 2 ? EPI_PITCH2 : EPI_PITCH4;
@@ -318,8 +330,8 @@ __device__ __forceinline__ void store_rows(const unsigned char* lds, OutT* Cb, i
     constexpr int RPI = GEMM_THREADS / PPR;              // rows per iteration
     const int r0 = t / PPR, c = t % PPR;
     const unsigned char* src = lds + r0 * PITCH + c * VB;
-    OutT* dst = Cb + (int64_t)(mbase + r0) * c_ld + n0 + c * EPV;
     const int n = n0 + c * EPV;
+    OutT* dst = Cb + (int64_t)(mbase + r0) * c_ld + col_offset(n, c_seg, c_seg_stride);
 #pragma unroll 4
     for (int it = 0; it < RP / RPI; ++it) {
       const int m = mbase + r0 + it * RPI;
@@ -341,7 +353,8 @@ __device__ __forceinline__ void store_rows(const unsigned char* lds, OutT* Cb, i
       const int id = t + GEMM_THREADS * it;
       const int r = id / 128, c = id % 128;
       const int m = mbase + r, n = n0 + c;
-      if (m < M && n < N) Cb[(int64_t)m * c_ld + n] = *reinterpret_cast<const OutT*>(lds + r * PITCH + c * ES);
+      if (m < M && n < N)
+        Cb[(int64_t)m * c_ld + col_offset(n, c_seg, c_seg_stride)] = *reinterpret_cast<const OutT*>(lds + r * PITCH + c * ES);
     }
   }
 }
@@ -351,7 +364,8 @@ __device__ __forceinline__ void store_rows(const unsigned char* lds, OutT* Cb, i
 template <typename OutT, typename BiasT, bool ALLOW_FULL = true>
 __device__ __forceinline__ void store_tile(f32x16_t (&acc)[2][2], unsigned char* lds, OutT* Cb, int64_t c_ld,
                                            int M, int N, int m0, int n0, const BiasT* bias, int bias_mode,
-                                           int act, float slope, int c_vec, int t) {
+                                           int act, float slope, int c_vec, int t, int c_seg = 0,
+                                           int64_t c_seg_stride = 0) {
   constexpr int RP = sizeof(OutT) == 2 ? 128 : 64;       // rows per pass
   const bool colb = bias && bias_mode == 2;
   const bool full = ALLOW_FULL && (colb || act == HFTA_ACT_TANH || act == HFTA_ACT_GELU);
@@ -368,13 +382,13 @@ __device__ __forceinline__ void store_tile(f32x16_t (&acc)[2][2], unsigned char*
     __syncthreads();
     const int mbase = m0 + pass * RP;
     if (c_vec == 16) {
-      if (interior) store_rows<OutT, 16, true>(lds, Cb, c_ld, M, N, mbase, n0, t);
-      else store_rows<OutT, 16, false>(lds, Cb, c_ld, M, N, mbase, n0, t);
+      if (interior) store_rows<OutT, 16, true>(lds, Cb, c_ld, M, N, mbase, n0, t, c_seg, c_seg_stride);
+      else store_rows<OutT, 16, false>(lds, Cb, c_ld, M, N, mbase, n0, t, c_seg, c_seg_stride);
     } else if (c_vec == 8) {
-      if (interior) store_rows<OutT, 8, true>(lds, Cb, c_ld, M, N, mbase, n0, t);
-      else store_rows<OutT, 8, false>(lds, Cb, c_ld, M, N, mbase, n0, t);
+      if (interior) store_rows<OutT, 8, true>(lds, Cb, c_ld, M, N, mbase, n0, t, c_seg, c_seg_stride);
+      else store_rows<OutT, 8, false>(lds, Cb, c_ld, M, N, mbase, n0, t, c_seg, c_seg_stride);
     } else {
-      store_rows<OutT, 0, false>(lds, Cb, c_ld, M, N, mbase, n0, t);
+      store_rows<OutT, 0, false>(lds, Cb, c_ld, M, N, mbase, n0, t, c_seg, c_seg_stride);
     }
     if (pass + 1 < 128 / RP) __syncthreads();
   }
@@ -458,7 +472,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs p) {
   const T* bias = p.bias ? reinterpret_cast<const T*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
   // bf16 operands with an fp32 result (weight gradients) never carry a column bias or a
   // transcendental activation (checked by the host)
-  store_tile<OutT, T, sizeof(T) == sizeof(OutT)>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t);
+  store_tile<OutT, T, sizeof(T) == sizeof(OutT)>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t, p.c_seg, p.c_seg_stride);
 }
 
 int gemm_pick_splits(const GemmDesc& d);

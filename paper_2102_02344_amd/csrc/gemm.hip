@@ -84,6 +84,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   a.bias_mode = d.bias ? d.bias_mode : 0;
   a.act = d.act; a.slope = d.slope;
   a.a_extent = a.b_extent = 0;
+  a.c_seg = d.c_seg; a.c_seg_stride = d.c_seg_stride;
 
   // vector-load eligibility: every address the fast path forms must be aligned
   const int es = (int)dtype_size(d.dtype);
@@ -108,6 +109,11 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
     return 0;
   };
   a.c_vec = store_bytes(d.C, d.c_ld, d.c_g0, d.c_g1);
+  if (d.c_seg > 0) {                 // a store piece must not straddle two column segments
+    if (splits > 1) return HFTA_EUNSUPPORTED;
+    while (a.c_vec >= 8 && (d.c_seg % (a.c_vec / oes) != 0 || d.c_seg_stride % (a.c_vec / oes) != 0)) a.c_vec >>= 1;
+    if (a.c_vec < 8) a.c_vec = 0;
+  }
   a.p_vec = splits > 1 ? store_bytes(d.partial, d.N, (int64_t)d.M * d.N, 0) : 0;
 
   // operand slice extents for the buffer-load kernels
@@ -131,7 +137,8 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   // Compute-bound problems (MLP-sized bf16 GEMMs) take the 256x256 kernel: it needs 16-byte
   // loadable operands, no split, a long reduction, and enough tiles to give every compute unit
   // at least one.
-  if ((v16 || (v8 && !d.a_kc && !d.b_kc)) && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 512) {
+  if ((v16 || (v8 && !d.a_kc && !d.b_kc)) && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 512 &&
+      (d.c_seg == 0 || a.c_vec >= 8)) {
     const int64_t t256 = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * G;
     if (t256 >= 192) {
       GemmArgs b = a;

@@ -57,7 +57,7 @@ __device__ __forceinline__ float big_act(float x, float neg_slope) {
 // pieces of a row, so a wavefront's store covers whole row segments.
 template <typename OutT, int THREADS>
 __device__ __forceinline__ void big_store_rows(const unsigned char* smem, OutT* Cb, int64_t c_ld, int M, int N,
-                                               int mbase, int n0, int c_vec, int t) {
+                                               int mbase, int n0, int c_vec, int t, int c_seg, int64_t c_seg_stride) {
   constexpr int ES = sizeof(OutT);
   constexpr int RP = ES == 2 ? 128 : 64;
   constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
@@ -68,7 +68,7 @@ __device__ __forceinline__ void big_store_rows(const unsigned char* smem, OutT* 
     for (int it = 0; it < RP / RPI; ++it) {
       const int rr = r0 + it * RPI, m = mbase + rr;
       const uint4 v = *reinterpret_cast<const uint4*>(smem + rr * PITCH + c * 16);
-      OutT* dst = Cb + (int64_t)m * c_ld + n;
+      OutT* dst = Cb + (int64_t)m * c_ld + col_offset(n, c_seg, c_seg_stride);
       if (m < M && n + EPV <= N) {
         *reinterpret_cast<uint4*>(dst) = v;
       } else if (m < M && n < N) {
@@ -85,7 +85,7 @@ __device__ __forceinline__ void big_store_rows(const unsigned char* smem, OutT* 
     for (int it = 0; it < RP / RPI; ++it) {
       const int rr = r0 + it * RPI, m = mbase + rr;
       const uint2 v = *reinterpret_cast<const uint2*>(smem + rr * PITCH + c * 8);
-      OutT* dst = Cb + (int64_t)m * c_ld + n;
+      OutT* dst = Cb + (int64_t)m * c_ld + col_offset(n, c_seg, c_seg_stride);
       if (m < M && n + EPV <= N && c_vec == 8) {
         *reinterpret_cast<uint2*>(dst) = v;
       } else if (m < M && n < N) {
@@ -332,7 +332,7 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
       }
     }
     __syncthreads();
-    big_store_rows<OutT, BIG_THREADS>(smem, Cb, p.c_ld, p.M, p.N, m0 + pass * RP, n0, p.c_vec, t);
+    big_store_rows<OutT, BIG_THREADS>(smem, Cb, p.c_ld, p.M, p.N, m0 + pass * RP, n0, p.c_vec, t, p.c_seg, p.c_seg_stride);
     if (pass + 1 < 256 / RP) __syncthreads();
   }
 }

@@ -177,7 +177,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_pf_kernel(GemmArgs p) {
   const T* bias = p.bias ? reinterpret_cast<const T*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
   // fp32 results of bf16 operands are weight gradients: the host never pairs them with a column bias
   // or a transcendental activation, and leaving that code out halves the kernel's registers
-  store_tile<OutT, T, sizeof(OutT) == 2>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t);
+  store_tile<OutT, T, sizeof(OutT) == 2>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t, p.c_seg, p.c_seg_stride);
 }
 
 int gemm_pf_launch(const GemmDesc& d, const GemmArgs& a, bool v16, dim3 grid, hipStream_t st);

