@@ -99,10 +99,12 @@ def kernel_label(name, a):
         return "colsum_kernel"
     if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
+    # the GAN array gives every convolution a workspace: column-buffer lowering, several kernels per call
     if name == "conv2d_grouped_fwd":
-        return "conv_gemm_kernel(fwd)"
-    if name == "conv2d_grouped_bwd":   # the GAN array asks for dX and dW in separate calls
-        return "conv_dx_kernel" if a[14] is not None else "conv_gemm_kernel(dW)+conv_splitk_reduce_kernel"
+        return "conv2d fwd: im2col_lds_kernel + gemm"
+    if name == "conv2d_grouped_bwd":   # dX and dW are asked for in separate calls
+        return ("conv2d dX: pack_dy_kernel + gemm + col2im_lds_kernel" if a[14] is not None
+                else "conv2d dW: pack_dy_kernel + im2col_lds_kernel + gemm")
     if name == "conv1x1_bwd":          # called with either dX or dW requested, never both
         k = "gemm_pf_kernel" if a[5] == 1 else "gemm_kernel"
         return k + ("(dX)" if a[11] is not None else "(dW)+splitk_reduce_kernel")
@@ -254,12 +256,18 @@ def ops_report(torch, binding):
         dY = torch.randn_like(Y)
         dX = torch.empty_like(X)
         dW = torch.empty(B * co, ci, 4, 4, device="cuda")
-        ws = torch.empty(max(4, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1)),
+        geo = (B, Nb, ci, co, H, H, 4, 4, 2, 1, 1)
+        ws = torch.empty(max(4, hb.conv2d_grouped_bwd_workspace_bytes(*geo), hb.conv2d_grouped_fwd_workspace_bytes(*geo)),
                          dtype=torch.uint8, device="cuda")
+        nmin = hb.conv2d_grouped_bwd_min_workspace_bytes(*geo)
+        wmin = torch.empty(nmin, dtype=torch.uint8, device="cuda") if nmin else None
         fl = 2.0 * B * Nb * Ho * Ho * ci * co * 16
-        for name, fn in (("conv2d_fwd", lambda: hb.conv2d_grouped_fwd(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1, X, W, None, Y)),
-                         ("conv2d_dX", lambda: hb.conv2d_grouped_bwd(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1, None, W, dY, dX, None, None, None)),
-                         ("conv2d_dW", lambda: hb.conv2d_grouped_bwd(B, Nb, ci, co, H, H, 4, 4, 2, 1, 1, X, None, dY, None, dW, None, ws))):
+        for name, fn in (("conv2d_fwd", lambda: hb.conv2d_grouped_fwd(*geo, X, W, None, Y, workspace=ws)),
+                         ("conv2d_dX", lambda: hb.conv2d_grouped_bwd(*geo, None, W, dY, dX, None, None, ws)),
+                         ("conv2d_dW", lambda: hb.conv2d_grouped_bwd(*geo, X, None, dY, None, dW, None, ws)),
+                         ("conv2d_fwd (implicit GEMM, no workspace)", lambda: hb.conv2d_grouped_fwd(*geo, X, W, None, Y)),
+                         ("conv2d_dX (implicit GEMM, no workspace)", lambda: hb.conv2d_grouped_bwd(*geo, None, W, dY, dX, None, None, None)),
+                         ("conv2d_dW (implicit GEMM, minimal workspace)", lambda: hb.conv2d_grouped_bwd(*geo, X, None, dY, None, dW, None, wmin))):
             t = timeit(fn)
             out.append(dict(op=name, workload=f"c3 B=10 Nb=64 {ci}->{co} {H}x{H} k4 s2 p1 bf16", ms=t * 1e3, bound="mfma",
                             achieved=fl / t / 1e12, peak=MFMA_PEAK, unit="TFLOP/s", frac=fl / t / 1e12 / MFMA_PEAK))

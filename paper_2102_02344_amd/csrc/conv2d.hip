@@ -810,7 +810,10 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   if (rc != HFTA_OK) return rc;
   if (!X || !Wt || !Y || !valid_act(act)) return HFTA_EINVAL;
   Lowered L;
-  if (workspace && reinterpret_cast<uintptr_t>(workspace) % 256 == 0 &&
+  // images of 16x16 outputs and more fill the implicit kernel's 128-column tiles by themselves, and
+  // it moves no column buffer: measured faster there; below that the sample-folded GEMM wins
+  const bool big_image = (int64_t)g.Ho * g.Wo >= 256;
+  if (!big_image && workspace && reinterpret_cast<uintptr_t>(workspace) % 256 == 0 &&
       lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L) && ws_bytes >= L.col_bytes) {
     rc = lowered_fwd(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, g, L, X, Wt, bias, Y, act, act_slope, workspace,
                      as_stream(stream));
@@ -863,7 +866,10 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   if (!dY || (dX && !Wt) || (dW && !X)) return HFTA_EINVAL;
   hipStream_t st = as_stream(stream);
   Lowered L;
-  if ((dX || dW) && workspace && reinterpret_cast<uintptr_t>(workspace) % 256 == 0 &&
+  // the data gradient of large images with enough channels stays on the implicit kernel (see the
+  // forward); everything else goes through the column buffer when the workspace allows
+  const bool implicit_dx = (int64_t)g.Ho * g.Wo >= 256 && Ci >= 32;
+  if ((dW || (dX && !implicit_dx)) && workspace && reinterpret_cast<uintptr_t>(workspace) % 256 == 0 &&
       lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L) && ws_bytes >= L.dcol_bytes + L.dyp_bytes + L.part_bytes) {
     unsigned char* wsb = reinterpret_cast<unsigned char*>(workspace);
     void* colb = wsb;
@@ -889,7 +895,7 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
       rc = gemm_launch(d, st);
       if (rc != HFTA_OK) return rc;
     }
-    if (dX) {
+    if (dX && !implicit_dx) {
       GemmDesc d{};
       d.S = 1; d.G0 = B; d.G1 = 1;
       d.A = Wt; d.Bm = dyp; d.C = colb;
@@ -904,16 +910,8 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
                               : launch_col2im_t<float>(colb, dX, B, Nb, Ci, H, W, g, kh, kw, stride, pad, st);
       if (rc != HFTA_OK) return rc;
     }
-    if (dbias) {
-      if (dtype == HFTA_BF16)
-        hipLaunchKernelGGL(conv_dbias_kernel<bf16_raw>, dim3((unsigned)(B * Co)), dim3(256), 0, st, (const bf16_raw*)dY,
-                           dbias, Nb, B * Co, L.HoWo);
-      else
-        hipLaunchKernelGGL(conv_dbias_kernel<float>, dim3((unsigned)(B * Co)), dim3(256), 0, st, (const float*)dY, dbias, Nb,
-                           B * Co, L.HoWo);
-      return launch_status();
-    }
-    return HFTA_OK;
+    dW = nullptr;                      // done; what is left (implicit dX, dbias) follows
+    if (!implicit_dx) dX = nullptr;
   }
   ConvArgs w = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
   if (dW) {
