@@ -221,6 +221,28 @@ int hfta_bn_bwd_maxpool(int B, int Nb, int C, int L, int dtype,
                         void* dX, const int64_t dxs[4], float* dgamma, float* dbeta, float* dx_sum,
                         int act, float act_slope, void* stream);
 
+/* Fused backward of  hfta_conv1x1_fwd -> hfta_bn_fwd_maxpool  (the last per-point layer of a
+ * point-cloud model: Conv1d k=1, BatchNorm, ReLU/LeakyReLU/none, max over points), bf16 only.
+ * X: the convolution's input (strides xs); W:[B][Co][Ci], bias:[B][Co] or NULL; Z: the
+ * convolution's output, read ONLY at the Nb*Co argmax points; dV, idx, vs: pooled gradient and
+ * argmax as in hfta_bn_bwd_maxpool.  Outputs dX (strides dxs, storage dtype), dW fp32 [B][Co][Ci],
+ * dbias fp32 [B][Co] or NULL (exactly zero: a bias in front of a BatchNorm), dgamma, dbeta.
+ * The dense [Nb][B*Co][L] gradient of the convolution output is never formed (BatchNorm's
+ * backward is a per-channel affine map of Z plus Nb spikes, so dX and dW reduce to a Ci x Ci Gram
+ * matrix of X, a Ci -> Ci convolution with the spikes scattered in, and gathers at the argmax
+ * points).  EUNSUPPORTED unless bf16, Ci <= 128, Ci % 8 == 0, Co <= 1024, L % 4 == 0, unit
+ * point strides; EWORKSPACE below hfta_conv1x1_bn_maxpool_bwd_workspace_bytes (256-byte aligned). */
+size_t hfta_conv1x1_bn_maxpool_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
+int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                                const void* X, const int64_t xs[4], const void* W, const void* bias,
+                                const void* Z, const int64_t zs[4], const void* dV, const int32_t* idx,
+                                const int64_t vs[3], const float* gamma, const float* beta,
+                                const float* save_mean, const float* save_invstd,
+                                void* dX, const int64_t dxs[4], float* dW, float* dbias,
+                                float* dgamma, float* dbeta, int act, float act_slope,
+                                void* workspace, size_t ws_bytes, void* stream);
+
+
 /* ------------------------------------------------------------------------
  * Fused Adam over the parameter arena of all B models (section "Our Proposal:
  * HFTA", paragraph on optimizers: a vector of per-model learning rates applied

@@ -113,7 +113,7 @@ class FusedPointNetCls(ParamArena):
     BN_EPS = 1e-5
     BN_MOMENTUM = 0.1
 
-    def __init__(self, spec, inp: dict, device: str = "cuda"):
+    def __init__(self, spec, inp: dict, device: str = "cuda", fused_tail: bool = True):
         self.spec = spec
         self.B, self.Nb, self.L = spec.B, spec.Nb, spec.L
         self.dtype = spec.dtype
@@ -159,6 +159,12 @@ class FusedPointNetCls(ParamArena):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nfc):
             ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt))
+        # the last per-point layer's backward (max-pool, BatchNorm, both conv gradients) as one operator
+        # that never forms the dense [Nb, B*C, L] gradient, where the library supports the shape
+        self.fused_tail_ws = 0
+        if fused_tail and self.nconv >= 2:
+            self.fused_tail_ws = hb.conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, spec.conv[-2], spec.conv[-1], L, self.dt)
+        ws = max(ws, self.fused_tail_ws)
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
 
         # ---- inputs -----------------------------------------------------------------
@@ -290,6 +296,21 @@ class FusedPointNetCls(ParamArena):
             k = f"conv{i}"
             cs = _cs(B, co, L)
             dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
+            if i == self.nconv - 1 and self.fused_tail_ws > 0:
+                xin, dxin = self.a[i - 1], self.dbuf[cur][:Nb * B * ci * L]
+                hb.conv1x1_bn_maxpool_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
+                                          self.z[i], cs, dpool, self.pool_idx, (Nb * co, co, 1),
+                                          self.master(k + ".bn.g"), self.master(k + ".bn.b"),
+                                          self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], dxin,
+                                          _cs(B, ci, L), self.g(k + ".w"), self.g(k + ".b"), self.g(k + ".bn.g"),
+                                          self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.ws)
+                P("conv1x1_bn_maxpool_bwd", layer=k, x=xin, w=self.w(k + ".w"), z=self.z[i],
+                  dv=dpool.view(B, Nb, co), idx=self.pool_idx, g=self.master(k + ".bn.g"),
+                  b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
+                  dx=dxin.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"), dg=self.g(k + ".bn.g"),
+                  dbt=self.g(k + ".bn.b"))
+                da = dxin
+                continue
             if i == self.nconv - 1:
                 hb.bn_bwd_maxpool(B, Nb, co, L, dt, self.z[i], cs, dpool, self.pool_idx, (Nb * co, co, 1),
                                   self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],

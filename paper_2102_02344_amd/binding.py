@@ -56,6 +56,8 @@ _SIGS = {
     "hfta_bn_bwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_bn_fwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
+    "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
+    "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 19 + [_i, _f, _p, _sz, _p]),
     "hfta_maxpool_points": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p]),
     "hfta_maxpool_points_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _s4, _p, _s4, _p]),
     "hfta_adam_step": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
@@ -212,6 +214,21 @@ def bn_bwd_maxpool(B, Nb, C_, L, dtype, X, xs, dV, idx, vs, gamma, beta, save_me
                                     _strides(vs, 3), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd),
                                     _ptr(dX), _strides(dxs), _ptr(dgamma), _ptr(dbeta), _ptr(dx_sum), act,
                                     act_slope, _stream(stream)), "hfta_bn_bwd_maxpool")
+
+
+def conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype) -> int:
+    return _lib.hfta_conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype)
+
+
+def conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, dV, idx, vs, gamma, beta, save_mean,
+                           save_invstd, dX, dxs, dW, dbias, dgamma, dbeta, act=ACT_NONE, act_slope=0.0,
+                           workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(bias),
+                                            _ptr(Z), _strides(zs), _ptr(dV), _ptr(idx), _strides(vs, 3), _ptr(gamma),
+                                            _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dX), _strides(dxs),
+                                            _ptr(dW), _ptr(dbias), _ptr(dgamma), _ptr(dbeta), act, act_slope, wp, wb,
+                                            _stream(stream)), "hfta_conv1x1_bn_maxpool_bwd")
 
 
 def maxpool_points(B, Nb, C_, L, dtype, X, xs, V, idx, vs, stream=None):

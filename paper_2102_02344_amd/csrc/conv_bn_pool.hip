@@ -1,0 +1,603 @@
+// Fused backward of  k=1 Conv1d -> BatchNorm (+ ReLU / LeakyReLU) -> max over points,
+// the tail of a point-cloud model's per-point MLP (fusion rules table rows "Conv1d" and
+// "BatchNorm1d" plus the point max-pool), without ever forming the dense gradient of the
+// convolution's [Nb, B*Co, L] output.
+//
+// The pooled gradient reaches the convolution output z only at the Nb argmax points of a channel,
+// so BatchNorm's backward is, per channel c (m = Nb*L, xhat = (z - mean) * invstd, a = gamma*invstd):
+//     dz[n,c,l] = s[n,c] * [l == idx[n,c]]  -  p0'[c]  -  p1[c] * z[n,c,l]
+//     s = a * dv * act'(.),  p1 = a*invstd*dgamma/m,  p0' = a*(dbeta - invstd*mean*dgamma)/m
+// with dbeta, dgamma sums over the Nb argmax elements only.  Substituting z = W x + bias:
+//     dX[n][:,l] = sum_{c: idx[n,c] = l} s[n,c] W[c,:]  -  v  -  G x[n][:,l]
+//         G = sum_c p1[c] W[c,:]^T W[c,:]   (Ci x Ci),   v = sum_c p0[c] W[c,:],  p0 = p0' + p1*bias
+//     dW[c,:]    = sum_n s[n,c] x[n][:, idx[n,c]]  -  a[c] (dbeta[c] E[x] + invstd dgamma[c] Cov(z_c, x))
+//         E[x] = SX / m,  Cov(z_c, x) = (W[c,:] XX + bias SX) / m - mean[c] E[x],  XX = sum_{n,l} x x^T,  SX = sum_{n,l} x
+// so the work is one Ci x Ci Gram matrix of the layer input (a split-K GEMM), one Ci -> Ci
+// convolution with a scatter of the argmax columns in its epilogue, and small per-model algebra:
+// the 1.3 GB tensor of the headline workload is neither read nor written.
+#include "gemm_pf.h"
+#include "bn_common.h"
+
+using namespace hfta;
+
+namespace {
+
+struct CbpChan { float a, dbeta, dgamma, invstd, mean, bias; };
+
+struct CbpArgs {
+  const bf16_raw* X; const bf16_raw* W; const bf16_raw* bias; const bf16_raw* Z; const bf16_raw* dV;
+  const int32_t* idx;
+  const float* gamma; const float* beta; const float* save_mean; const float* save_invstd;
+  bf16_raw* dX; float* dW; float* dbias; float* dgamma; float* dbeta;
+  int64_t xsb, xsn, xsc, zsb, zsn, zsc, vsb, vsn, vsc, dxsb, dxsn, dxsc;
+  int B, Nb, Ci, Co, L, act;
+  float slope;
+  // workspace
+  CbpChan* chan;      // [B][Co]
+  float* p0;          // [B][Co]
+  float* p1;          // [B][Co]
+  float* s;           // [B][Nb][Co]
+  float* XX;          // [B][Ci][Ci]
+  float* SX;          // [B][Ci]
+  bf16_raw* negG;     // [B][Ci][Ci]
+  float* v;           // [B][Ci]
+  bf16_raw* xg;       // [B][Nb][Co][Ci]: the input column at each argmax point
+  float* SXpart;      // [B][Nb][tiles][Ci]
+  uint32_t* skey;     // [B][Nb][Co]: argmax positions sorted by point, point << 10 | channel
+  float* sval;        // [B][Nb][Co]: s in that order
+  int* toff;          // [B][Nb][tiles + 1]: where each 128-point tile starts in the sorted order
+  int c_vec;
+  uint32_t x_extent, g_extent;
+};
+
+// ---- per channel: dbeta, dgamma from the Nb argmax elements; coefficients ----------------
+__global__ __launch_bounds__(64) void cbp_coef_kernel(CbpArgs p) {
+  const int c = blockIdx.x, b = blockIdx.y, k = b * p.Co + c;
+  const int lane = threadIdx.x;
+  const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
+  float s1 = 0.f, s2 = 0.f;
+  for (int n = lane; n < p.Nb; n += 64) {
+    const int hit = min(max(p.idx[b * p.vsb + n * p.vsn + c * p.vsc], 0), p.L - 1);
+    const float z = bf16_to_f32(p.Z[b * p.zsb + n * p.zsn + c * p.zsc + hit]);
+    const float xh = (z - mean) * invstd;
+    const float gr = bf16_to_f32(p.dV[b * p.vsb + n * p.vsn + c * p.vsc]) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+    s1 += gr;
+    s2 = fmaf(gr, xh, s2);
+    p.s[((int64_t)b * p.Nb + n) * p.Co + c] = gr;          // scaled by a below
+  }
+  s1 = wave_sum(s1);
+  s2 = wave_sum(s2);
+  const float a = g * invstd;
+  const float m = (float)p.Nb * (float)p.L;
+  const float bias = p.bias ? bf16_to_f32(p.bias[k]) : 0.f;
+  for (int n = lane; n < p.Nb; n += 64) p.s[((int64_t)b * p.Nb + n) * p.Co + c] *= a;
+  if (lane == 0) {
+    p.dbeta[k] = s1;
+    p.dgamma[k] = s2;
+    if (p.dbias) p.dbias[k] = 0.f;                          // a bias in front of a BatchNorm: gradient exactly zero
+    p.chan[k] = CbpChan{a, s1, s2, invstd, mean, bias};
+    p.p1[k] = a * invstd * s2 / m;
+    p.p0[k] = a * (s1 + invstd * s2 * (bias - mean)) / m;
+  }
+}
+
+// ---- argmax positions of one (model, sample) sorted by point, ties in channel order ------------
+// key = point << 10 | channel (Co <= 1024, L < 2^21: checked on the host); bitonic sort in LDS.
+// toff[tile] = first sorted position whose point lies in 128-point tile `tile` or later.
+__global__ __launch_bounds__(512) void cbp_sort_kernel(CbpArgs p, int P, int tiles) {
+  __shared__ uint32_t key[1024];
+  const int n = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+  for (int c = t; c < P; c += 512) {
+    uint32_t k = 0xffffffffu;
+    if (c < p.Co) {
+      const int hit = min(max(p.idx[b * p.vsb + n * p.vsn + c * p.vsc], 0), p.L - 1);
+      k = ((uint32_t)hit << 10) | (uint32_t)c;
+    }
+    key[c] = k;
+  }
+  for (int k = 2; k <= P; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      __syncthreads();
+      for (int i = t; i < P / 2; i += 512) {
+        const int lo = 2 * (i & ~(j - 1)) + (i & (j - 1)), hi = lo + j;
+        const uint32_t x = key[lo], y = key[hi];
+        if ((x > y) == ((lo & k) == 0)) { key[lo] = y; key[hi] = x; }
+      }
+    }
+  __syncthreads();
+  const int64_t base = ((int64_t)b * p.Nb + n) * p.Co;
+  for (int c = t; c < p.Co; c += 512) {
+    const uint32_t k = key[c];
+    p.skey[base + c] = k;
+    p.sval[base + c] = p.s[base + (k & 1023u)];
+  }
+  int* toff = p.toff + ((int64_t)b * p.Nb + n) * (tiles + 1);
+  for (int k = t; k <= p.Co; k += 512) {
+    const int cur = k < p.Co ? (int)(key[k] >> 17) : tiles;
+    const int prev = k > 0 ? (int)(key[k - 1] >> 17) : -1;
+    for (int tl = prev + 1; tl <= cur; ++tl) toff[tl] = k;
+  }
+}
+
+// ---- G = sum_c p1[c] W[c,:]^T W[c,:] (stored negated, bf16) and v = sum_c p0[c] W[c,:] --------
+// One workgroup per 32 x 32 tile of G and model, fp32 matrix instructions (the operands are exact
+// in fp32); the eight wavefronts take an eighth of the channels each and are added in order.
+constexpr int GW_WAVES = 8;
+__global__ __launch_bounds__(GW_WAVES * 64) void cbp_gram_w_kernel(CbpArgs p) {
+  __shared__ float red[GW_WAVES][16][64];
+  __shared__ float vred[GW_WAVES][32];
+  const int T = (p.Ci + 31) / 32;
+  const int ti = blockIdx.x / T, tj = blockIdx.x % T, b = blockIdx.y;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int i = lane & 31, kh = lane >> 5;
+  const int ca = ti * 32 + i, cb = tj * 32 + i;
+  const float ma = ca < p.Ci ? 1.f : 0.f, mb = cb < p.Ci ? 1.f : 0.f;
+  const bf16_raw* Wa = p.W + (int64_t)b * p.Co * p.Ci + min(ca, p.Ci - 1);
+  const bf16_raw* Wc = p.W + (int64_t)b * p.Co * p.Ci + min(cb, p.Ci - 1);
+  const float* P1 = p.p1 + b * p.Co;
+  const float* P0 = p.p0 + b * p.Co;
+  const int per = ((p.Co + 2 * GW_WAVES - 1) / (2 * GW_WAVES)) * 2;      // channels per wavefront, even
+  const int c_lo = wave * per, c_hi = min(p.Co, c_lo + per);
+  f32x16_t acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  float vacc = 0.f;
+  for (int c2 = c_lo; c2 < c_hi; c2 += 16) {
+    float wa[8], wb[8], q1[8], q0[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {                        // unconditional loads at a clamped channel, masked below
+      const int c = c2 + 2 * u + kh;
+      const int cc = min(c, c_hi - 1);
+      const float live = c < c_hi ? 1.f : 0.f;
+      wa[u] = bf16_to_f32(Wa[(int64_t)cc * p.Ci]) * (ma * live);
+      wb[u] = bf16_to_f32(Wc[(int64_t)cc * p.Ci]) * mb;
+      q1[u] = P1[cc];
+      q0[u] = P0[cc];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(q1[u] * wa[u], wb[u], acc, 0, 0, 0);
+      vacc = fmaf(q0[u], wa[u], vacc);
+    }
+  }
+  vacc += __shfl_xor(vacc, 32, 64);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[v];
+  if (lane < 32) vred[wave][lane] = vacc;
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 16 * 64 / (GW_WAVES * 64); ++r) {
+    const int o = t + GW_WAVES * 64 * r, v = o >> 6, ln = o & 63;
+    float g = 0.f;
+#pragma unroll
+    for (int w = 0; w < GW_WAVES; ++w) g += red[w][v][ln];
+    const int ci = ti * 32 + 8 * (v >> 2) + 4 * (ln >> 5) + (v & 3), cj = tj * 32 + (ln & 31);
+    if (ci < p.Ci && cj < p.Ci) p.negG[((int64_t)b * p.Ci + ci) * p.Ci + cj] = f32_to_bf16(-g);
+  }
+  if (tj == 0 && t < 32 && ti * 32 + t < p.Ci) {
+    float vs = 0.f;
+#pragma unroll
+    for (int w = 0; w < GW_WAVES; ++w) vs += vred[w][t];
+    p.v[(int64_t)b * p.Ci + ti * 32 + t] = vs;
+  }
+}
+
+// ---- dX tile = -(G x) - v + argmax columns.  Also emits, for the weight gradient, the input
+// ---- column x[:, idx] of every argmax that falls in the tile and the tile's row sums of x. ----
+template <int KT>
+__global__ __launch_bounds__(GEMM_THREADS) void cbp_dx_kernel(CbpArgs p) {
+  constexpr int PITCH = KT * 2 + 16;
+  constexpr int TILE = 128 * PITCH;
+  constexpr int STAGE = 64 * EPI_PITCH4;                 // fp32 staging of 64 rows
+  constexpr int GREG = TILE > STAGE ? TILE : STAGE;
+  constexpr int SUB = KT / 32;
+  constexpr int WP = KT * 2;                             // pitch of a staged W row
+  constexpr int HC = TILE / WP;                          // W rows that fit where the X tile was
+  constexpr int PRE = 16;                                // W rows per wavefront fetched ahead into registers
+  __shared__ __attribute__((aligned(16))) unsigned char smem[TILE + GREG];
+  __shared__ unsigned short hit_c[1024];               // this tile's argmax hits (Co <= 1024 on the host):
+  __shared__ unsigned char hit_q[1024];                // channel, column inside the tile, gradient value;
+  __shared__ float hit_s[1024];                        // sorted by column, channel order inside a column
+  __shared__ float sxs[256];
+  unsigned char* Xs = smem;
+  unsigned char* Gs = smem + TILE;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int bx = blockIdx.x, bz = blockIdx.z;
+  {  // XCD-aware renumbering (see gemm_kernel)
+    const int total = gridDim.x * gridDim.z, per = total >> 3;
+    const int lin = blockIdx.x + gridDim.x * blockIdx.z;
+    if (lin < (per << 3)) {
+      const int l2 = (lin & 7) * per + (lin >> 3);
+      bz = l2 / gridDim.x;
+      bx = l2 - bz * gridDim.x;
+    }
+  }
+  const int b = bz / p.Nb, n = bz % p.Nb;
+  const int l0 = bx * 128;
+  const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + b * p.xsb + n * p.xsn, p.x_extent);
+  const __amdgpu_buffer_rsrc_t rg = pf_rsrc(p.negG + (int64_t)b * p.Ci * p.Ci, p.g_extent);
+  const int* toff = p.toff + (int64_t)bz * (gridDim.x + 1);
+  const int k0 = toff[bx], nh = toff[bx + 1] - k0;
+  const uint32_t* skey = p.skey + (int64_t)bz * p.Co + k0;
+  const float* sval = p.sval + (int64_t)bz * p.Co + k0;
+  const bf16_raw* Wb = p.W + (int64_t)b * p.Co * p.Ci;
+
+  {  // X tile, transposed in registers into [point][ci]
+    const int kq = t % 8, ng = t / 8;
+    const int c = l0 + ng * 4;
+    const uint32_t ldb = (uint32_t)(p.xsc * 2);
+    uint2 q[SUB][4];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = s * 32 + 4 * kq + j;
+        const bool ok = k < p.Ci && c + 4 <= p.L;
+        const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? (uint32_t)k * ldb + (uint32_t)c * 2u : PF_OOB), 0, 0);
+        q[s][j] = make_uint2(v.x, v.y);
+      }
+    // the tile's hit list rides along with the tile loads
+    const uint32_t key0 = t < nh ? skey[t] : 0u;
+    const float sv0 = t < nh ? sval[t] : 0.f;
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+      const uint32_t a0 = q[s][0].x, a1 = q[s][1].x, a2 = q[s][2].x, a3 = q[s][3].x;
+      const uint32_t b0 = q[s][0].y, b1 = q[s][1].y, b2 = q[s][2].y, b3 = q[s][3].y;
+      uint2 o[4];
+      o[0] = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
+      o[1] = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
+      o[2] = make_uint2((b0 & 0xffffu) | (b1 << 16), (b2 & 0xffffu) | (b3 << 16));
+      o[3] = make_uint2((b0 >> 16) | (b1 & 0xffff0000u), (b2 >> 16) | (b3 & 0xffff0000u));
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<uint2*>(Xs + (ng * 4 + i) * PITCH + s * 64 + kq * 8) = o[i];
+    }
+    if (t < nh) {
+      hit_c[t] = (unsigned short)(key0 & 1023u); hit_q[t] = (unsigned char)((int)(key0 >> 10) - l0); hit_s[t] = sv0;
+    }
+    for (int i = t + GEMM_THREADS; i < nh; i += GEMM_THREADS) {
+      const uint32_t k = skey[i];
+      hit_c[i] = (unsigned short)(k & 1023u); hit_q[i] = (unsigned char)((int)(k >> 10) - l0); hit_s[i] = sval[i];
+    }
+  }
+  {  // -G rows (k-contiguous)
+    const int wr = t >> 2, wg = (t & 3) * 8;
+#pragma unroll
+    for (int s = 0; s < SUB; ++s)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int row = wr + 64 * h, k = s * 32 + wg;
+        const bool ok = row < p.Ci && k + 8 <= p.Ci;
+        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rg, (int)(ok ? ((uint32_t)row * (uint32_t)p.Ci + (uint32_t)k) * 2u : PF_OOB), 0, 0);
+        *reinterpret_cast<uint4*>(Gs + row * PITCH + k * 2) = make_uint4(v.x, v.y, v.z, v.w);
+      }
+  }
+  __syncthreads();
+
+  // W rows of the first hits: fetched now, parked in LDS once the X tile is dead
+  uint32_t wpre[PRE];
+#pragma unroll
+  for (int r = 0; r < PRE; ++r) {
+    const int i = wave + 4 * r;
+    wpre[r] = 0u;
+    if (i < nh && 2 * lane < p.Ci) wpre[r] = reinterpret_cast<const uint32_t*>(Wb + (int64_t)hit_c[i] * p.Ci)[lane];
+  }
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const int r = lane & 31, gsel = lane >> 5;
+#pragma unroll
+  for (int s = 0; s < KT / 16; ++s) {
+    bf16x8_t a[2], bb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      a[i] = *reinterpret_cast<const bf16x8_t*>(Gs + (wm * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
+      bb[i] = *reinterpret_cast<const bf16x8_t*>(Xs + (wn * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j], a[i], acc[i][j], 0, 0, 0);
+  }
+
+  {  // this tile's part of sum_l x: thread (ci, half) adds 64 points in order
+    const int ci = t & 127, half = t >> 7;
+    float sx = 0.f;
+    if (ci < KT) {
+      const unsigned char* col = Xs + (half * 64) * PITCH + ci * 2;
+#pragma unroll 8
+      for (int q = 0; q < 64; ++q) sx += bf16_to_f32(*reinterpret_cast<const bf16_raw*>(col + q * PITCH));
+    }
+    sxs[t] = sx;
+  }
+  // input columns at the argmax points, for the weight gradient's gather term
+#pragma unroll 4
+  for (int h = wave; h < nh; h += 4) {
+    const uint32_t* xrow = reinterpret_cast<const uint32_t*>(Xs + hit_q[h] * PITCH);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(p.xg + ((int64_t)bz * p.Co + hit_c[h]) * p.Ci);
+    if (2 * lane < p.Ci) dst[lane] = xrow[lane];
+  }
+  __syncthreads();                                       // both tiles are dead from here on
+
+  if (t < 128 && t < p.Ci) p.SXpart[((int64_t)bz * gridDim.x + bx) * p.Ci + t] = sxs[t] + sxs[t + 128];
+  bf16_raw* dXb = p.dX + b * p.dxsb + n * p.dxsn;
+  float* stage = reinterpret_cast<float*>(Gs);
+  unsigned char* Wh = Xs;
+  constexpr int SP = EPI_PITCH4 / 4;                     // staging pitch in floats
+  const int ml = lane & 31, nq = (lane >> 5) * 4;
+
+  // W rows kc .. kc+kn of the hit list into LDS (row i of the chunk at Wh + i * WP); lanes past Ci write zeros
+  auto load_rows = [&](int kc, int kn, int first) {
+    for (int i = wave + 4 * first; i < kn; i += 4) {
+      uint32_t w = 0u;
+      if (2 * lane < p.Ci) w = reinterpret_cast<const uint32_t*>(Wb + (int64_t)hit_c[kc + i] * p.Ci)[lane];
+      if (4 * lane < WP) *reinterpret_cast<uint32_t*>(Wh + i * WP + lane * 4) = w;
+    }
+  };
+#pragma unroll
+  for (int r2 = 0; r2 < PRE; ++r2) {
+    const int i = wave + 4 * r2;
+    if (i < nh && i < HC && 4 * lane < WP) *reinterpret_cast<uint32_t*>(Wh + i * WP + lane * 4) = wpre[r2];
+  }
+  load_rows(0, min(nh, HC), PRE);
+  int resident = 0;                                      // first hit of the chunk that sits in Wh
+
+  // ---- two passes of 64 output rows: stage fp32 (dense part), add the columns, store as bf16
+#pragma unroll 1
+  for (int pass = 0; pass < 2; ++pass) {
+    if (wm == pass) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int rl = i * 32 + ml;
+        const int m = pass * 64 + rl;
+        const float vm = m < p.Ci ? p.v[(int64_t)b * p.Ci + m] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int nl = wn * 64 + j * 32 + 8 * q + nq;
+            *reinterpret_cast<float4*>(stage + rl * SP + nl) =
+                make_float4(acc[i][j][4 * q] - vm, acc[i][j][4 * q + 1] - vm, acc[i][j][4 * q + 2] - vm,
+                            acc[i][j][4 * q + 3] - vm);
+          }
+      }
+    }
+    __syncthreads();                                     // staged rows and W rows in place
+    if (pass * 64 < p.Ci) {
+#pragma unroll 1
+      for (int kc = 0; kc < nh; kc += HC) {
+        const int kn = min(HC, nh - kc);
+        if (kc != resident) {
+          load_rows(kc, kn, 0);
+          resident = kc;
+          __syncthreads();
+        }
+        // the wavefronts split the chunk at column boundaries; one lane per output row walks its
+        // share in order: a column's hits in channel order, then one update of the staged cell
+        int ka = kc + (kn * wave) / 4, ke = kc + (kn * (wave + 1)) / 4;
+        while (ka > kc && ka < kc + kn && hit_q[ka] == hit_q[ka - 1]) ++ka;
+        while (ke > kc && ke < kc + kn && hit_q[ke] == hit_q[ke - 1]) ++ke;
+        const unsigned char* wcol = Wh + (pass * 64 + lane) * 2 - kc * WP;
+        if (ka < ke) {
+          int col = hit_q[ka];
+          float val = 0.f;
+#pragma unroll 4
+          for (int k = ka; k < ke; ++k) {                // the loads of several hits are in flight together
+            const int q = hit_q[k];
+            const float sv = hit_s[k];
+            const float w = bf16_to_f32(*reinterpret_cast<const bf16_raw*>(wcol + k * WP));
+            if (q != col) {
+              stage[lane * SP + col] += val;
+              val = 0.f;
+              col = q;
+            }
+            val = fmaf(sv, w, val);
+          }
+          stage[lane * SP + col] += val;
+        }
+        __syncthreads();
+      }
+    }
+    // 64 rows x 128 columns out as bf16: 4-column (8-byte) pieces, consecutive lanes on consecutive pieces
+#pragma unroll
+    for (int it = 0; it < 64 * 32 / GEMM_THREADS; ++it) {
+      const int id = t + GEMM_THREADS * it;
+      const int rr = id >> 5, cp = id & 31;
+      const int m = pass * 64 + rr, l = l0 + cp * 4;
+      const float4 f = *reinterpret_cast<const float4*>(stage + rr * SP + cp * 4);
+      if (m < p.Ci && l < p.L) {
+        bf16_raw* d = dXb + (int64_t)m * p.dxsc + l;
+        if (p.c_vec >= 8 && l + 4 <= p.L) {
+          *reinterpret_cast<uint2*>(d) = make_uint2(pack_bf16x2(f.x, f.y), pack_bf16x2(f.z, f.w));
+        } else {
+          const float e[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (l + k < p.L) d[k] = f32_to_bf16(e[k]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ---- SX[b][ci] = sum over (n, l) of x, from the per-tile sums, in a fixed order -----------------
+__global__ __launch_bounds__(1024) void cbp_sx_kernel(CbpArgs p, int parts) {
+  __shared__ float red[64][16];
+  const int b = blockIdx.y, cl = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const int ci = blockIdx.x * 16 + cl;
+  const float* src = p.SXpart + (int64_t)b * parts * p.Ci;
+  float s = 0.f;
+  if (ci < p.Ci) {
+#pragma unroll 4
+    for (int q = g; q < parts; q += 64) s += src[(int64_t)q * p.Ci + ci];
+  }
+  red[g][cl] = s;
+  __syncthreads();
+  if (g == 0 && ci < p.Ci) {
+    float tot = 0.f;
+    for (int k = 0; k < 64; ++k) tot += red[k][cl];
+    p.SX[(int64_t)b * p.Ci + ci] = tot;
+  }
+}
+
+// ---- dW[c][:] = gather term - a (dbeta E[x] + invstd dgamma Cov(z_c, x)), 8 channels per workgroup ----
+__global__ __launch_bounds__(128) void cbp_dw_kernel(CbpArgs p) {
+  constexpr int CB = 8;
+  __shared__ float wrow[CB][128];
+  const int c0 = blockIdx.x * CB, b = blockIdx.y, cj = threadIdx.x;
+  for (int e = cj; e < CB * p.Ci; e += 128) {
+    const int cc = e / p.Ci, k = e - cc * p.Ci;
+    wrow[cc][k] = c0 + cc < p.Co ? bf16_to_f32(p.W[((int64_t)b * p.Co + c0 + cc) * p.Ci + k]) : 0.f;
+  }
+  __syncthreads();
+  if (cj >= p.Ci) return;
+  const float* XXb = p.XX + (int64_t)b * p.Ci * p.Ci;
+  float T[CB];
+#pragma unroll
+  for (int e = 0; e < CB; ++e) T[e] = 0.f;
+#pragma unroll 8
+  for (int ci = 0; ci < p.Ci; ++ci) {                    // Ci is a multiple of 8 (host)
+    const float x = XXb[(int64_t)ci * p.Ci + cj];
+#pragma unroll
+    for (int e = 0; e < CB; ++e) T[e] = fmaf(wrow[e][ci], x, T[e]);
+  }
+  const double m = (double)p.Nb * (double)p.L;
+  const double sx = (double)p.SX[(int64_t)b * p.Ci + cj], ex = sx / m;
+#pragma unroll 1
+  for (int e = 0; e < CB; ++e) {
+    const int c = c0 + e;
+    if (c >= p.Co) break;
+    float sp = 0.f;
+#pragma unroll 8
+    for (int n = 0; n < p.Nb; ++n) {
+      const int64_t row = ((int64_t)b * p.Nb + n) * p.Co + c;
+      sp = fmaf(p.s[row], bf16_to_f32(p.xg[row * p.Ci + cj]), sp);
+    }
+    const CbpChan ch = p.chan[b * p.Co + c];
+    const double ezx = ((double)T[e] + (double)ch.bias * sx) / m;
+    const double dense = (double)ch.a * ((double)ch.dbeta * ex + (double)ch.invstd * (double)ch.dgamma * (ezx - (double)ch.mean * ex));
+    p.dW[((int64_t)b * p.Co + c) * p.Ci + cj] = (float)((double)sp - dense);
+  }
+}
+
+size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct CbpLayout { size_t chan, p0, p1, s, XX, SX, negG, v, xg, SXpart, skey, sval, toff, part, total; };
+
+GemmDesc gram_desc(int B, int Nb, int Ci, int L, const void* X, const int64_t xs[4], float* XX) {
+  GemmDesc d{};
+  d.A = X; d.Bm = X; d.C = XX;
+  d.M = Ci; d.N = Ci; d.K = L; d.S = Nb; d.G0 = B; d.G1 = 1;
+  d.a_kc = true; d.a_ld = xs[2]; d.a_ss = xs[1]; d.a_g0 = xs[0];
+  d.b_kc = true; d.b_ld = xs[2]; d.b_ss = xs[1]; d.b_g0 = xs[0];
+  d.c_ld = Ci; d.c_g0 = (int64_t)Ci * Ci;
+  d.act = HFTA_ACT_NONE; d.dtype = HFTA_BF16; d.out_f32 = true; d.splits = 1;
+  return d;
+}
+
+CbpLayout cbp_layout(int B, int Nb, int Ci, int Co, int L) {
+  CbpLayout w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += a256(bytes); return o; };
+  w.chan = take((size_t)B * Co * sizeof(CbpChan));
+  w.p0 = take((size_t)B * Co * 4);
+  w.p1 = take((size_t)B * Co * 4);
+  w.s = take((size_t)B * Nb * Co * 4);
+  w.XX = take((size_t)B * Ci * Ci * 4);
+  w.SX = take((size_t)B * Ci * 4);
+  w.negG = take((size_t)B * Ci * Ci * 2);
+  w.v = take((size_t)B * Ci * 4);
+  w.xg = take((size_t)B * Nb * Co * Ci * 2);
+  w.SXpart = take((size_t)B * Nb * ((L + 127) / 128) * Ci * 4);
+  w.skey = take((size_t)B * Nb * Co * 4);
+  w.sval = take((size_t)B * Nb * Co * 4);
+  w.toff = take((size_t)B * Nb * ((L + 127) / 128 + 1) * 4);
+  const int64_t unit[4] = {(int64_t)Ci * L, (int64_t)B * Ci * L, L, 1};
+  GemmDesc d = gram_desc(B, Nb, Ci, L, nullptr, unit, nullptr);
+  w.part = take(gemm_partial_bytes(d, gemm_pick_splits(d)));
+  w.total = off;
+  return w;
+}
+
+bool cbp_supported(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  return dtype == HFTA_BF16 && B > 0 && Nb > 0 && Ci > 0 && Co > 0 && L > 0 && Ci <= 128 && Ci % 8 == 0 && Co <= 1024 &&
+         L % 4 == 0 && L < (1 << 21) && Nb <= 65535 && B <= 65535 && (int64_t)B * Nb <= 65535;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t hfta_conv1x1_bn_maxpool_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  if (!cbp_supported(B, Nb, Ci, Co, L, dtype)) return 0;
+  return cbp_layout(B, Nb, Ci, Co, L).total;
+}
+
+int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                                const void* W, const void* bias, const void* Z, const int64_t zs[4], const void* dV,
+                                const int32_t* idx, const int64_t vs[3], const float* gamma, const float* beta,
+                                const float* save_mean, const float* save_invstd, void* dX, const int64_t dxs[4],
+                                float* dW, float* dbias, float* dgamma, float* dbeta, int act, float act_slope,
+                                void* workspace, size_t ws_bytes, void* stream) {
+  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !W || !Z || !zs || !dV ||
+      !idx || !vs || !gamma || !beta || !save_mean || !save_invstd || !dX || !dxs || !dW || !dgamma || !dbeta)
+    return HFTA_EINVAL;
+  if (!(act == HFTA_ACT_NONE || act == HFTA_ACT_RELU || act == HFTA_ACT_LEAKY)) return HFTA_EUNSUPPORTED;
+  if (!cbp_supported(B, Nb, Ci, Co, L, dtype) || xs[3] != 1 || zs[3] != 1 || dxs[3] != 1) return HFTA_EUNSUPPORTED;
+  auto al = [](const void* q, size_t a) { return (reinterpret_cast<uintptr_t>(q) % a) == 0; };
+  if (!al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0 || !al(W, 4)) return HFTA_EUNSUPPORTED;
+  const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2;
+  if (x_ext >= (int64_t)1 << 31) return HFTA_EUNSUPPORTED;
+  const CbpLayout lay = cbp_layout(B, Nb, Ci, Co, L);
+  if (!workspace || !al(workspace, 256) || ws_bytes < lay.total) return HFTA_EWORKSPACE;
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  hipStream_t st = as_stream(stream);
+
+  CbpArgs a{};
+  a.X = (const bf16_raw*)X; a.W = (const bf16_raw*)W; a.bias = (const bf16_raw*)bias; a.Z = (const bf16_raw*)Z;
+  a.dV = (const bf16_raw*)dV; a.idx = idx;
+  a.gamma = gamma; a.beta = beta; a.save_mean = save_mean; a.save_invstd = save_invstd;
+  a.dX = (bf16_raw*)dX; a.dW = dW; a.dbias = dbias; a.dgamma = dgamma; a.dbeta = dbeta;
+  a.xsb = xs[0]; a.xsn = xs[1]; a.xsc = xs[2]; a.zsb = zs[0]; a.zsn = zs[1]; a.zsc = zs[2];
+  a.vsb = vs[0]; a.vsn = vs[1]; a.vsc = vs[2]; a.dxsb = dxs[0]; a.dxsn = dxs[1]; a.dxsc = dxs[2];
+  a.B = B; a.Nb = Nb; a.Ci = Ci; a.Co = Co; a.L = L; a.act = act; a.slope = act_slope;
+  a.chan = (CbpChan*)(ws + lay.chan); a.p0 = (float*)(ws + lay.p0); a.p1 = (float*)(ws + lay.p1);
+  a.s = (float*)(ws + lay.s); a.XX = (float*)(ws + lay.XX); a.SX = (float*)(ws + lay.SX);
+  a.negG = (bf16_raw*)(ws + lay.negG); a.v = (float*)(ws + lay.v); a.xg = (bf16_raw*)(ws + lay.xg); a.SXpart = (float*)(ws + lay.SXpart);
+  a.skey = (uint32_t*)(ws + lay.skey); a.sval = (float*)(ws + lay.sval); a.toff = (int*)(ws + lay.toff);
+  a.c_vec = (al(dX, 8) && dxs[0] % 4 == 0 && dxs[1] % 4 == 0 && dxs[2] % 4 == 0) ? 8 : 0;
+  a.x_extent = (uint32_t)x_ext; a.g_extent = (uint32_t)((int64_t)Ci * Ci * 2);
+
+  hipLaunchKernelGGL(cbp_coef_kernel, dim3((unsigned)Co, (unsigned)B), dim3(64), 0, st, a);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  // Gram matrix of the layer input: XX[b] = sum_{n,l} x x^T, through the batched GEMM core
+  GemmDesc g = gram_desc(B, Nb, Ci, L, X, xs, a.XX);
+  g.splits = gemm_pick_splits(g);
+  g.partial = (float*)(ws + lay.part);
+  int rc = gemm_launch(g, st);
+  if (rc != HFTA_OK) return rc;
+  const int T32 = (Ci + 31) / 32;
+  hipLaunchKernelGGL(cbp_gram_w_kernel, dim3((unsigned)(T32 * T32), (unsigned)B), dim3(GW_WAVES * 64), 0, st, a);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
+  int P = 2;
+  while (P < Co) P <<= 1;
+  hipLaunchKernelGGL(cbp_sort_kernel, dim3((unsigned)Nb, (unsigned)B), dim3(512), 0, st, a, P, (int)grid.x);
+  if (Ci <= 64) hipLaunchKernelGGL(cbp_dx_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
+  else hipLaunchKernelGGL(cbp_dx_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  hipLaunchKernelGGL(cbp_sx_kernel, dim3((unsigned)((Ci + 15) / 16), (unsigned)B), dim3(1024), 0, st, a, Nb * (int)grid.x);
+  hipLaunchKernelGGL(cbp_dw_kernel, dim3((unsigned)((Co + 7) / 8), (unsigned)B), dim3(128), 0, st, a);
+  return launch_status();
+}
+
+}  // extern "C"

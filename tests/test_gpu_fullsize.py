@@ -27,12 +27,14 @@ def rel_ok(got, ref, tol, what):
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} samples beyond tol, worst {np.abs(got - ref)[bad].max():.3e}"
 
 
-def test_c1_full_size_step_sampled():
-    """Config 1 as benchmarked: B=8, bf16, 32 clouds x 2500 points per model."""
+@pytest.mark.parametrize("fused_tail", [True, False])
+def test_c1_full_size_step_sampled(fused_tail):
+    """Config 1 as benchmarked: B=8, bf16, 32 clouds x 2500 points per model (``fused_tail`` is the
+    benchmark's configuration; the unfused tail is the path other storage types take)."""
     from paper_2102_02344_amd.arrays import FusedPointNetCls
     spec = hi.spec_c1()
     inp = hi.pointnet_cls_inputs(spec)
-    arr = FusedPointNetCls(spec, inp)
+    arr = FusedPointNetCls(spec, inp, fused_tail=fused_tail)
     B, Nb, L = spec.B, spec.Nb, spec.L
     rng = np.random.default_rng(5)
     tol = TOL["bf16"]
@@ -114,9 +116,54 @@ def test_c1_full_size_step_sampled():
             rel_ok(f64(kw["dx"][nt, bt * Ci + ct, lt]), (dys * ws).sum(axis=1), tol, "conv4 dX")
             seen.append(op + lay)
 
+        elif op == "conv1x1_bn_maxpool_bwd":
+            print("full-size check", op, flush=True)
+            x, z = kw["x"], kw["z"]
+            Ci, Co = x.shape[1] // B, z.shape[1] // B
+            M = Nb * L
+            w = f64(kw["w"].view(B, Co, Ci))
+            g, bt_ = f64(kw["g"]).reshape(B, 1, Co), f64(kw["b"]).reshape(B, 1, Co)
+            mean, invstd = f64(kw["mean"]).reshape(B, 1, Co), f64(kw["invstd"]).reshape(B, 1, Co)
+            dv, idx = f64(kw["dv"]), kw["idx"].long()                                        # [B, Nb, Co]
+            # the gradient lives only at the argmax positions: everything per channel follows from
+            # the Nb values of z there (max-pool backward, then ReLU on the normalised value)
+            zc = z.view(Nb, B, Co, L)
+            z_at = f64(torch.gather(zc, 3, idx.permute(1, 0, 2).unsqueeze(3))[..., 0].permute(1, 0, 2))
+            xh_at = (z_at - mean) * invstd
+            gr = np.where(g * xh_at + bt_ > 0, dv, 0.0)                                      # [B, Nb, Co]
+            dbeta, dgamma = gr.sum(axis=1), (gr * xh_at).sum(axis=1)                         # [B, Co]
+            sc = np.abs(dv).sum(axis=1)
+            assert np.all(np.abs(f64(kw["dbt"]).reshape(B, Co) - dbeta) <= 2e-4 * np.maximum(np.abs(dbeta), 1e-2 * sc))
+            assert np.all(np.abs(f64(kw["dg"]).reshape(B, Co) - dgamma) <= 2e-4 * np.maximum(np.abs(dgamma), 1e-2 * sc))
+            a = g[:, 0] * invstd[:, 0]                                                       # [B, Co]
+            idx_h = idx.cpu().numpy()
+            # weight gradient of sampled (b, o, c): dense BatchNorm backward of channel (b, o), then the
+            # full reduction over (n, l) against input channel (b, c)
+            dw = kw["dw"].view(B, Co, Ci)
+            for b, o, c in zip(rng.integers(0, B, 24), rng.integers(0, Co, 24), rng.integers(0, Ci, 24)):
+                xh = (chan(z, b, Co, o) - mean[b, 0, o]) * invstd[b, 0, o]
+                dz = -(dbeta[b, o] + xh * dgamma[b, o]) / M
+                dz[np.arange(Nb), idx_h[b, :, o]] += gr[b, :, o]
+                dz *= a[b, o]
+                xc = chan(x, b, Ci, c)
+                ref, terms = (dz * xc).sum(), np.abs(dz * xc).sum()
+                assert abs(float(dw[b, o, c]) - ref) <= tol * max(abs(ref), 1e-2 * terms), "fused tail dW"
+            # data gradient at sampled (n, b, c, l): all Co channels of the BatchNorm backward at that point
+            S = 2000
+            n, b, c, l = (rng.integers(0, m, S) for m in (Nb, B, Ci, L))
+            nt, bt, lt = (torch.from_numpy(v).cuda() for v in (n, b, l))
+            co = torch.arange(Co, device="cuda")
+            zs = f64(z[nt[:, None], (bt * Co)[:, None] + co[None, :], lt[:, None]])          # [S, Co]
+            xh = (zs - mean[b, 0]) * invstd[b, 0]
+            dz = -(dbeta[b] + xh * dgamma[b]) / M + np.where(idx_h[b, n] == l[:, None], gr[b, n], 0.0)
+            ref = (a[b] * dz * w[b, :, c]).sum(axis=1)
+            rel_ok(f64(kw["dx"][nt, bt * Ci + torch.from_numpy(c).cuda(), lt]), ref, tol, "fused tail dX")
+            seen.append(op)
+
     arr.forward_backward(probe)
     torch.cuda.synchronize()
-    assert set(seen) == {"conv1x1_fwdconv0", "conv1x1_fwdconv4", "bn_fwd_maxpool", "bn_bwd_maxpool", "conv1x1_bwdconv4"}
+    tail = {"conv1x1_bn_maxpool_bwd"} if fused_tail else {"bn_bwd_maxpool", "conv1x1_bwdconv4"}
+    assert set(seen) == {"conv1x1_fwdconv0", "conv1x1_fwdconv4", "bn_fwd_maxpool"} | tail
     assert np.all(np.isfinite(arr.loss.cpu().numpy()))
     # Adam over the whole arena, in full, from the gradients the GPU just produced
     th0, g = f64(arr.theta), f64(arr.grad)

@@ -513,3 +513,85 @@ def test_bn_maxpool_fused(hb, dtype, B, Nb, C, L):
     hb.maxpool_points_bwd(B, Nb, C, L, DT[dtype], dV, I, vs, dYd, s)
     hb.bn_bwd(B, Nb, C, L, DT[dtype], X, s, dYd, s, G, Bt, SM, SI, dX2, s, dG2, dB2, hb.ACT_RELU, 0.0)
     check(host(dX), host(dX2), 1e-5 if dtype == "f32" else 8e-3, "fused vs unfused dX")
+
+
+# ------------------------------------------------------------------ conv1x1 -> BatchNorm -> point max-pool, fused backward
+@pytest.mark.parametrize("B,Nb,Ci,Co,L,act", [(2, 5, 16, 40, 300, 1), (2, 3, 128, 136, 260, 1), (3, 4, 64, 72, 132, 2),
+                                               (1, 2, 8, 1024, 8, 0)])
+def test_conv1x1_bn_maxpool_bwd_fused(hb, B, Nb, Ci, Co, L, act):
+    """The fused backward never forms the dense [Nb, B*Co, L] gradient; it must equal the chain
+    point-max backward -> BatchNorm backward -> conv1x1 backward of the oracle, and the library's
+    own unfused chain, to the bf16 tolerance (the references round the dense gradient to bf16
+    before the two contractions, the fused operator has no such tensor)."""
+    dtype = "bf16"
+    print(f"conv+bn+pool bwd B={B} Nb={Nb} Ci={Ci} Co={Co} L={L} act={act}", flush=True)
+    x = hi.snap(np.maximum(hi.normal(131, (Nb, B * Ci, L)) + 0.3, 0.0), dtype)      # like a post-ReLU activation
+    w = hi.normal(132, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    bias = hi.normal(133, (B * Co,), dtype, 0.1)
+    g = (hi.normal(134, (B * Co,)) * 0.3 + 1.0).astype(np.float32)
+    g[0] = -abs(g[0])
+    bt = (hi.normal(135, (B * Co,)) * 0.3).astype(np.float32)
+    slope = 0.2
+    oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
+    z = oops.store(oa.conv1x1_fwd(B, x, w, bias), dtype)
+    ry, rmean, rinv, _, _ = oa.bn_fwd(B, z, g, bt, 1e-5)
+    ya = oops.store(oops.act_fwd(ry, oact, slope), dtype)
+    rv, ri = oa.maxpool_points_fwd(B, ya)
+    dv = hi.normal(136, (B, Nb, Co), dtype)
+    sx, sz = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    vs = (Nb * Co, Co, 1)
+    t3 = lambda a: np.ascontiguousarray(a.reshape(Nb, B, Co).transpose(1, 0, 2))
+    idx = t3(ri).astype(np.int32)
+    mean32, inv32 = rmean.astype(np.float32), rinv.astype(np.float32)
+    # oracle chain
+    dy = oa.maxpool_points_bwd(B, dv.transpose(1, 0, 2).reshape(Nb, B * Co), ri, L)
+    gdy = oops.act_bwd(ry, dy, oact, slope)
+    rdz, rdg, rdb = oa.bn_bwd(B, z, gdy, g, mean32, inv32)
+    rdx, rdw, _ = oa.conv1x1_bwd(B, x, w, rdz)                 # exact composition (no rounding of dz)
+    rdx_r, rdw_r, _ = oa.conv1x1_bwd(B, x, w, oops.store(rdz, dtype))
+    X, W, Bi, Z = dev(x, dtype), dev(w, dtype), dev(bias, dtype), dev(z, dtype)
+    G, Bt, SM, SI = dev(g), dev(bt), dev(mean32), dev(inv32)
+    dV, I = dev(dv, dtype), torch.from_numpy(idx).cuda()
+    dX = empty(x.shape, dtype)
+    dW = empty((B * Co, Ci), torch.float32)
+    dB0, dG, dBt = (empty((B * Co,), torch.float32) for _ in range(3))
+    nws = hb.conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype])
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bi, Z, sz, dV, I, vs, G, Bt, SM, SI, dX, sx, dW,
+                              dB0, dG, dBt, act, slope, ws)
+    sc = np.abs(dv).sum(axis=1).max()
+    assert np.abs(host(dG) - rdg).max() <= f32_tol(dtype) * max(np.abs(rdg).max(), sc * 1e-2), "dgamma"
+    assert np.abs(host(dBt) - rdb).max() <= f32_tol(dtype) * max(np.abs(rdb).max(), sc * 1e-2), "dbeta"
+    assert float(dB0.abs().max()) == 0.0
+    # Conditioning term: the operator normalises the convolution output it recomputes from X and W
+    # (through the Gram matrix), the chain normalises the stored, bf16-rounded z.  The two differ by
+    # at most 2^-9 |z| per element, which the dense term scales by gamma * invstd^2 * dgamma / M.
+    M = Nb * L
+    coef = np.abs(g * rinv * rinv * rdg) / M * 2.0 ** -9                       # [B*Co]
+    xa, za = np.abs(x).reshape(Nb, B, Ci, L), np.abs(z).reshape(Nb, B, Co, L)
+    cf, wa = coef.reshape(B, Co), np.abs(w).reshape(B, Co, Ci)
+    ex_dw = (cf[:, :, None] * np.einsum("nbcl,nbil->bci", za, xa)).reshape(B * Co, Ci)
+    ex_dx = np.einsum("bci,nbcl->nbil", wa * cf[:, :, None], za).reshape(Nb, B * Ci, L)
+    e1 = check(host(dX), rdx, TOL[dtype], "dX vs exact composition", ex_dx)
+    e2 = check(host(dW), rdw, TOL[dtype], "dW vs exact composition", ex_dw)
+    e3 = check(host(dX), rdx_r, TOL[dtype], "dX vs chain with stored dz", ex_dx)
+    e4 = check(host(dW), rdw_r, TOL[dtype], "dW vs chain with stored dz", ex_dw)
+    raw = lambda a, r: np.abs(a - r).max() / np.abs(r).max()
+    print(f"   raw norm-wise err: dX {raw(host(dX), rdx):.2e}, dW {raw(host(dW), rdw):.2e}", flush=True)
+    assert raw(host(dX), rdx) <= TOL[dtype] and raw(host(dW), rdw) <= TOL[dtype]
+    print(f"   conditioning allowance / rms: dX {ex_dx.max() / np.sqrt((rdx ** 2).mean()):.2e}, "
+          f"dW {ex_dw.max() / np.sqrt((rdw ** 2).mean()):.2e}", flush=True)
+    print(f"   rel err: dX {e1:.2e} / {e3:.2e}, dW {e2:.2e} / {e4:.2e}", flush=True)
+    # the library's own unfused chain on the same inputs
+    dZ = empty(z.shape, dtype)
+    dG2, dB2 = empty((B * Co,), torch.float32), empty((B * Co,), torch.float32)
+    hb.bn_bwd_maxpool(B, Nb, Co, L, DT[dtype], Z, sz, dV, I, vs, G, Bt, SM, SI, dZ, sz, dG2, dB2, act, slope)
+    dX2 = empty(x.shape, dtype)
+    dW2 = empty((B * Co, Ci), torch.float32)
+    n2 = hb.conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype])
+    ws2 = torch.empty(max(n2, 4), dtype=torch.uint8, device="cuda")
+    hb.conv1x1_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, dZ, sz, dX2, sx, dW2, None, ws2)
+    check(host(dX), host(dX2), 2 * TOL[dtype], "fused vs unfused dX", ex_dx)    # both sides carry their own bf16 rounding
+    check(host(dW), host(dW2), 2 * TOL[dtype], "fused vs unfused dW", ex_dw)
+    assert torch.equal(dG, dG2) or np.abs(host(dG) - host(dG2)).max() <= 1e-5 * max(np.abs(rdg).max(), sc * 1e-2)
