@@ -181,6 +181,34 @@ def maxpool_points_bwd(B, dv, idx, L):
     return dx
 
 
+# ---------------------------------------------------------------- conv1x1 -> BatchNorm -> act -> point max, one operator
+def conv1x1_bn_maxpool_fwd(B, x, w, bias, gamma, beta, eps=1e-5, momentum=0.1, running_mean=None,
+                           running_var=None, act=1, slope=0.2):
+    """x:[N, B*Ci, L], w:[B*Co, Ci] -> (v[N,B*Co], idx, mean, invstd, new_rm, new_rv, zhit[N,B*Co])."""
+    Ci, Co = x.shape[1] // B, w.shape[0] // B
+    r = []
+    for b in range(B):
+        so = slice(b * Co, (b + 1) * Co)
+        r.append(ops.conv1x1_bn_maxpool_fwd(
+            _chan(x, b, Ci), w[so], None if bias is None else bias[so], gamma[so], beta[so], eps, momentum,
+            None if running_mean is None else running_mean[so], None if running_var is None else running_var[so],
+            act, slope))
+    cat = lambda j, ax: None if r[0][j] is None else np.concatenate([q[j] for q in r], axis=ax)
+    return cat(0, 1), cat(1, 1), cat(2, 0), cat(3, 0), cat(4, 0), cat(5, 0), cat(6, 1)
+
+
+def conv1x1_bn_maxpool_bwd(B, x, w, bias, gamma, beta, mean, invstd, dv, idx, act=1, slope=0.2):
+    """dv, idx:[N, B*Co] -> (dx[N,B*Ci,L], dw[B*Co,Ci], dbias[B*Co], dgamma[B*Co], dbeta[B*Co])."""
+    Ci, Co = x.shape[1] // B, w.shape[0] // B
+    r = []
+    for b in range(B):
+        so = slice(b * Co, (b + 1) * Co)
+        r.append(ops.conv1x1_bn_maxpool_bwd(_chan(x, b, Ci), w[so], None if bias is None else bias[so], gamma[so],
+                                            beta[so], mean[so], invstd[so], dv[:, so], idx[:, so], act, slope))
+    return (np.concatenate([q[0] for q in r], axis=1),) + tuple(np.concatenate([q[j] for q in r], axis=0)
+                                                                  for j in range(1, 5))
+
+
 # ---------------------------------------------------------------- losses
 def softmax_xent(B, logits, labels):
     """logits:[B, R, K], labels:[B, R] -> (loss[B], dlogits[B,R,K]); each model's

@@ -280,6 +280,36 @@ def maxpool_points_bwd(dv, idx, L: int):
 
 
 # --------------------------------------------------------------------------
+# Tail of a point-cloud model's per-point MLP as ONE operator:
+#   k=1 Conv1d -> training-mode BatchNorm -> activation -> max over points
+# (rows "Conv1d", "BatchNorm1d" and the element-wise rows, then the point max-pool).  It is the
+# composition of the definitions above with nothing stored between the steps: an operator that
+# keeps no intermediate tensor in memory has no storage rounding inside it.
+# --------------------------------------------------------------------------
+def conv1x1_bn_maxpool_fwd(x, w, bias, gamma, beta, eps: float = 1e-5, momentum: float = 0.1,
+                           running_mean=None, running_var=None, act: int = 1, slope: float = 0.2):
+    """x:[N,Ci,L], w:[Co,Ci].  Returns (v[N,Co], idx[N,Co], mean, invstd, new_running_mean,
+    new_running_var, zhit[N,Co]) with zhit the convolution output at the argmax point."""
+    z = conv1x1_fwd(x, w, bias)
+    y, mean, invstd, nrm, nrv = bn_fwd(z, gamma, beta, eps, momentum, running_mean, running_var)
+    v, idx = maxpool_points_fwd(act_fwd(y, act, slope))
+    zhit = np.take_along_axis(z, idx[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    return v, idx, mean, invstd, nrm, nrv, zhit
+
+
+def conv1x1_bn_maxpool_bwd(x, w, bias, gamma, beta, mean, invstd, dv, idx, act: int = 1, slope: float = 0.2):
+    """Backward of the operator above from the gradient dv[N,Co] of its pooled output: max-pool
+    scatter -> activation -> BatchNorm -> convolution.  Returns (dx, dw, dbias, dgamma, dbeta)."""
+    z = conv1x1_fwd(x, w, bias)
+    y = _f64(gamma)[None, :, None] * (z - _f64(mean)[None, :, None]) * _f64(invstd)[None, :, None] \
+        + _f64(beta)[None, :, None]
+    dy = act_bwd(y, maxpool_points_bwd(dv, idx, z.shape[2]), act, slope)
+    dz, dgamma, dbeta = bn_bwd(z, dy, gamma, mean, invstd)
+    dx, dw, db = conv1x1_bwd(x, w, dz)
+    return dx, dw, db, dgamma, dbeta
+
+
+# --------------------------------------------------------------------------
 # Activations (rows "ReLU", "LeakyReLU", "Tanh"; GELU for the MLP workload)
 # --------------------------------------------------------------------------
 ACT_NONE, ACT_RELU, ACT_LEAKY, ACT_TANH, ACT_GELU = 0, 1, 2, 3, 4

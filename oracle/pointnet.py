@@ -16,7 +16,11 @@ mean reduction over the model's own batch; Adam.
 Storage rounding: every activation / activation-gradient tensor that the
 library keeps in memory between two operators is rounded once to the storage
 dtype (``ops.store``); statistics, parameter gradients and optimiser state are
-float32; arithmetic inside an operator is float64.
+float32; arithmetic inside an operator is float64.  With ``fused_tail`` the last
+per-point layer, its BatchNorm, ReLU and the max over points are ONE operator
+(``ops.conv1x1_bn_maxpool_fwd`` / ``_bwd``), forward and backward: it keeps no
+[N, C, L] tensor, so nothing inside it is rounded; only its pooled output and
+its input gradient are stored.
 """
 from __future__ import annotations
 
@@ -41,7 +45,7 @@ def init_state(params: Dict[str, np.ndarray]) -> Dict[str, Dict[str, np.ndarray]
 
 
 def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
-                     bn_eps=1e-5, bn_momentum=0.1):
+                     bn_eps=1e-5, bn_momentum=0.1, fused_tail=False):
     """Forward + backward of one model.
 
     points:[Nb,3,L], labels:[Nb], drop_mask:[Nb,F] or None.
@@ -60,10 +64,20 @@ def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
     # ---------------- forward: per-point MLP
     a = np.asarray(points, np.float64)
     for i in range(nconv):
-        z = S(ops.conv1x1_fwd(a, lp[f"conv{i}.w"], lp[f"conv{i}.b"]))
         rm = rv = None
         if running is not None:
             rm, rv = running[f"conv{i}.bn.rm"], running[f"conv{i}.bn.rv"]
+        if fused_tail and i == nconv - 1:
+            pooled, idx, mean, invstd, nrm, nrv, _ = ops.conv1x1_bn_maxpool_fwd(
+                a, lp[f"conv{i}.w"], lp[f"conv{i}.b"], lp[f"conv{i}.bn.g"], lp[f"conv{i}.bn.b"], bn_eps,
+                bn_momentum, rm, rv, ops.ACT_RELU)
+            mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
+            if running is not None:
+                new_running[f"conv{i}.bn.rm"], new_running[f"conv{i}.bn.rv"] = nrm, nrv
+            saved[f"conv{i}"] = (a, None, None, mean, invstd)
+            pooled = S(pooled)
+            break
+        z = S(ops.conv1x1_fwd(a, lp[f"conv{i}.w"], lp[f"conv{i}.b"]))
         y, mean, invstd, nrm, nrv = ops.bn_fwd(z, lp[f"conv{i}.bn.g"], lp[f"conv{i}.bn.b"],
                                                bn_eps, bn_momentum, rm, rv)
         mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
@@ -71,7 +85,8 @@ def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
             new_running[f"conv{i}.bn.rm"], new_running[f"conv{i}.bn.rv"] = nrm, nrv
         saved[f"conv{i}"] = (a, z, y, mean, invstd)
         a = S(ops.act_fwd(y, ops.ACT_RELU))
-    pooled, idx = ops.maxpool_points_fwd(a)
+    if not fused_tail:
+        pooled, idx = ops.maxpool_points_fwd(a)
     Lp = a.shape[2]
 
     # ---------------- forward: head
@@ -132,9 +147,18 @@ def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
         d = S(dx)
 
     # ---------------- backward: pool and per-point MLP
-    d = ops.maxpool_points_bwd(d, idx, Lp)      # exact scatter of stored values
+    if not fused_tail:
+        d = ops.maxpool_points_bwd(d, idx, Lp)      # exact scatter of stored values
     for i in reversed(range(nconv)):
         ain, z, y, mean, invstd = saved[f"conv{i}"]
+        if fused_tail and i == nconv - 1:
+            k = f"conv{i}"
+            dx, dw, db, dg, dbt = ops.conv1x1_bn_maxpool_bwd(ain, lp[k + ".w"], lp[k + ".b"], lp[k + ".bn.g"],
+                                                             lp[k + ".bn.b"], mean, invstd, d, idx, ops.ACT_RELU)
+            grads[k + ".bn.g"], grads[k + ".bn.b"], grads[k + ".w"], grads[k + ".b"] = dg, dbt, dw, db
+            if i > 0:
+                d = S(dx)
+            continue
         dy = ops.act_bwd(y, d, ops.ACT_RELU)
         dz, dg, dbt = ops.bn_bwd(z, dy, lp[f"conv{i}.bn.g"], mean, invstd)
         grads[f"conv{i}.bn.g"], grads[f"conv{i}.bn.b"] = dg, dbt
@@ -147,10 +171,10 @@ def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
                 running=new_running)
 
 
-def train_step(spec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None):
+def train_step(spec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, fused_tail=False):
     """One fwd + bwd + Adam step of one model; updates ``state`` in place.
     hp: dict(lr, beta1, beta2, eps, wd) scalars.  Returns the forward/backward dict."""
-    out = forward_backward(spec, state["theta"], points, labels, drop_mask, state["running"])
+    out = forward_backward(spec, state["theta"], points, labels, drop_mask, state["running"], fused_tail=fused_tail)
     for k in state["theta"]:
         g = ops.store(out["grads"][k], "f32")
         th, m, v = ops.adam_step(state["theta"][k], g, state["m"][k], state["v"][k],
@@ -163,12 +187,12 @@ def train_step(spec, state, points, labels, hp: Dict[str, float], t: int, drop_m
     return out
 
 
-def array_train_step(spec, states: List[dict], inp: dict, t: int):
+def array_train_step(spec, states: List[dict], inp: dict, t: int, fused_tail=False):
     """The array's reference: B separate unfused runs, one after another."""
     outs = []
     for b in range(spec.B):
         hp = {k: float(inp[k][b]) for k in ("lr", "beta1", "beta2", "eps", "wd")}
         mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
         outs.append(train_step(spec, states[b], inp["points"][:, 3 * b:3 * b + 3, :],
-                               inp["labels"][b], hp, t, mask))
+                               inp["labels"][b], hp, t, mask, fused_tail))
     return outs

@@ -378,3 +378,49 @@ def test_round_bf16_matches_definition():
     import torch
     assert np.array_equal(ops.round_bf16(r), r)
     assert np.array_equal(r, torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy())
+
+
+# ------------------------------------------------------------------ conv1x1 -> BatchNorm -> act -> point max, one operator
+@pytest.mark.parametrize("act", [ops.ACT_NONE, ops.ACT_RELU, ops.ACT_LEAKY])
+def test_conv_bn_maxpool_operator(act):
+    """Pins of the one-operator tail: brute-force loops for the forward; the statistics in closed
+    form from the input's first and second moments (mean = w E[x] + b, var = w Cov(x) w^T);
+    central finite differences of sum(v * r) for every gradient; the bias gradient is zero
+    because BatchNorm removes any per-channel constant."""
+    N, Ci, Co, L = 3, 4, 5, 7
+    x, w, b = rnd(N, Ci, L), rnd(Co, Ci), rnd(Co)
+    g, bt = rnd(Co), rnd(Co)
+    g[0] = -abs(g[0])                                   # a negative scale: the maximum sits at the minimum of z
+    eps, slope = 1e-3, 0.3
+    v, idx, mean, invstd, nrm, nrv, zhit = ops.conv1x1_bn_maxpool_fwd(x, w, b, g, bt, eps, 0.1, np.zeros(Co), np.ones(Co),
+                                                                        act, slope)
+    # brute force
+    m = N * L
+    for c in range(Co):
+        zs = [[sum(w[c, i] * x[n, i, l] for i in range(Ci)) + b[c] for l in range(L)] for n in range(N)]
+        mu = sum(sum(r) for r in zs) / m
+        var = sum(sum((q - mu) ** 2 for q in r) for r in zs) / m
+        assert abs(mean[c] - mu) < 1e-12 and abs(invstd[c] - 1 / math.sqrt(var + eps)) < 1e-10
+        assert abs(nrm[c] - 0.1 * mu) < 1e-12 and abs(nrv[c] - (0.9 + 0.1 * var * m / (m - 1))) < 1e-12
+        for n in range(N):
+            ys = [g[c] * (q - mu) / math.sqrt(var + eps) + bt[c] for q in zs[n]]
+            if act == ops.ACT_RELU:
+                ys = [max(q, 0.0) for q in ys]
+            elif act == ops.ACT_LEAKY:
+                ys = [q if q > 0 else slope * q for q in ys]
+            best = max(range(L), key=lambda l: (ys[l], -l))
+            assert idx[n, c] == best and abs(v[n, c] - ys[best]) < 1e-12 and abs(zhit[n, c] - zs[n][best]) < 1e-12
+    # closed form of the statistics from the moments of x
+    xf = x.transpose(1, 0, 2).reshape(Ci, -1)
+    ex, cov = xf.mean(axis=1), np.cov(xf, bias=True)
+    close(mean, w @ ex + b, 1e-12)
+    close(1 / invstd ** 2 - eps, np.einsum("ci,ij,cj->c", w, cov, w), 1e-12)
+    # gradients by central differences of sum(v * r); the argmax is locally constant
+    r = rnd(N, Co)
+    dx, dw, db, dg, dbt = ops.conv1x1_bn_maxpool_bwd(x, w, b, g, bt, mean, invstd, r, idx, act, slope)
+    f = lambda x_, w_, b_, g_, bt_: float((ops.conv1x1_bn_maxpool_fwd(x_, w_, b_, g_, bt_, eps, 0.1, None, None, act, slope)[0] * r).sum())
+    close(dx, fd_grad(lambda q: f(q, w, b, g, bt), x), 1e-5)
+    close(dw, fd_grad(lambda q: f(x, q, b, g, bt), w), 1e-5)
+    close(dg, fd_grad(lambda q: f(x, w, b, q, bt), g), 1e-5)
+    close(dbt, fd_grad(lambda q: f(x, w, b, g, q), bt), 1e-5)
+    assert np.abs(db).max() < 1e-12 and np.abs(fd_grad(lambda q: f(x, w, q, g, bt), b)).max() < 1e-6

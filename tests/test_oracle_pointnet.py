@@ -41,8 +41,10 @@ def torch_model_loss(spec, tp, points, labels, mask):
     return F.cross_entropy(h, torch.tensor(np.asarray(labels, np.int64))), h
 
 
-@pytest.mark.parametrize("fc_bn,p", [(True, 0.3), (False, 0.0)])
-def test_forward_backward_vs_autograd(fc_bn, p):
+@pytest.mark.parametrize("fc_bn,p,fused_tail", [(True, 0.3, False), (False, 0.0, False), (True, 0.3, True)])
+def test_forward_backward_vs_autograd(fc_bn, p, fused_tail):
+    """``fused_tail`` only changes where storage rounding happens: in float64 it must give the
+    same loss, logits and gradients (checked against autograd like the unfused reading)."""
     spec = tiny_spec(fc_bn, p)
     inp = hi.pointnet_cls_inputs(spec, seed=5)
     for b in range(spec.B):
@@ -50,7 +52,7 @@ def test_forward_backward_vs_autograd(fc_bn, p):
                  for k, v in inp["params"][b].items()}
         pts = inp["points"][:, 3 * b:3 * b + 3, :]
         mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
-        out = opn.forward_backward(spec, theta, pts, inp["labels"][b], mask)
+        out = opn.forward_backward(spec, theta, pts, inp["labels"][b], mask, fused_tail=fused_tail)
         tp = {k: T(v).requires_grad_() for k, v in theta.items()}
         loss, logits = torch_model_loss(spec, tp, pts, inp["labels"][b], mask)
         loss.backward()
