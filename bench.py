@@ -36,7 +36,8 @@ class Tracer:
     SINGLE_KERNEL = ("conv1x1_fwd", "conv1x1_bwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
                      "adam_step_multi", "linear_fwd", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
                      "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd",
-                     "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_bwd")
+                     "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_fwd",
+                     "conv1x1_bn_maxpool_bwd")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -113,8 +114,10 @@ def kernel_label(name, a):
         return k + ("(dX)" if a[11] is not None else "(dW)+splitk_reduce_kernel")
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
+    if name == "conv1x1_bn_maxpool_fwd":
+        return "conv1x1_bn_maxpool_fwd: fbp_main_kernel + gemm_pf_kernel(gram) + 3 small"
     if name == "conv1x1_bn_maxpool_bwd":
-        return "conv1x1_bn_maxpool_bwd: cbp_*_kernel x6 + gemm_pf_kernel(gram)"
+        return "conv1x1_bn_maxpool_bwd: cbp_dx_kernel + 5 small" + ("" if a[13] is not None else " + gemm_pf_kernel(gram)")
     return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",
             "adam_step_multi": "adam_multi_kernel"}[name]
 
@@ -133,9 +136,12 @@ def algorithmic_flops(name, a):
     if name in ("conv1x1_fwd", "conv1x1_bwd"):
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * Co * L
-    if name == "conv1x1_bn_maxpool_bwd":      # Gram matrix of the input + the Ci -> Ci product of the data gradient
+    if name == "conv1x1_bn_maxpool_fwd":      # the Ci -> Co product (its output is reduced, never stored) + the Gram matrix
         B, Nb, Ci, Co, L = a[:5]
-        return 4.0 * B * Nb * Ci * Ci * L
+        return 2.0 * B * Nb * Ci * (Co + Ci) * L
+    if name == "conv1x1_bn_maxpool_bwd":      # the Ci -> Ci product of the data gradient (+ the Gram matrix if not saved)
+        B, Nb, Ci, Co, L = a[:5]
+        return (2.0 if a[13] is not None else 4.0) * B * Nb * Ci * Ci * L
     if name in ("conv2d_grouped_fwd", "conv2d_grouped_bwd"):
         B, Nb, Ci, Co, H, W, kh, kw, st, pad = a[:10]
         Ho, Wo = (H + 2 * pad - kh) // st + 1, (W + 2 * pad - kw) // st + 1
@@ -168,6 +174,9 @@ def algorithmic_bytes(name, a):
         if a[11] is not None:          # dX = W^T dY: dY and W in, dX out
             return (B * Nb * (Ci + Co) * L + B * Co * Ci) * _es(dt)
         return B * Nb * (Ci + Co) * L * _es(dt) + B * Co * Ci * 4      # dW (fp32) = dY X^T
+    if name == "conv1x1_bn_maxpool_fwd":      # x in, W in, pooled + argmax + z at the argmax out
+        B, Nb, Ci, Co, L, dt = a[:6]
+        return B * Nb * Ci * L * _es(dt) + B * Co * Ci * _es(dt) + B * Nb * Co * (_es(dt) + 4 + 4)
     if name == "conv1x1_bn_maxpool_bwd":      # x in, dx out, W in, dW (fp32) out, pooled gradient + argmax in
         B, Nb, Ci, Co, L, dt = a[:6]
         return 2 * B * Nb * Ci * L * _es(dt) + B * Co * Ci * (_es(dt) + 4) + B * Nb * Co * (_es(dt) + 4 + _es(dt))

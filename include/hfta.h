@@ -221,22 +221,51 @@ int hfta_bn_bwd_maxpool(int B, int Nb, int C, int L, int dtype,
                         void* dX, const int64_t dxs[4], float* dgamma, float* dbeta, float* dx_sum,
                         int act, float act_slope, void* stream);
 
-/* Fused backward of  hfta_conv1x1_fwd -> hfta_bn_fwd_maxpool  (the last per-point layer of a
- * point-cloud model: Conv1d k=1, BatchNorm, ReLU/LeakyReLU/none, max over points), bf16 only.
- * X: the convolution's input (strides xs); W:[B][Co][Ci], bias:[B][Co] or NULL; Z: the
- * convolution's output, read ONLY at the Nb*Co argmax points; dV, idx, vs: pooled gradient and
- * argmax as in hfta_bn_bwd_maxpool.  Outputs dX (strides dxs, storage dtype), dW fp32 [B][Co][Ci],
- * dbias fp32 [B][Co] or NULL (exactly zero: a bias in front of a BatchNorm), dgamma, dbeta.
- * The dense [Nb][B*Co][L] gradient of the convolution output is never formed (BatchNorm's
- * backward is a per-channel affine map of Z plus Nb spikes, so dX and dW reduce to a Ci x Ci Gram
- * matrix of X, a Ci -> Ci convolution with the spikes scattered in, and gathers at the argmax
- * points).  EUNSUPPORTED unless bf16, Ci <= 128, Ci % 8 == 0, Co <= 1024, L % 4 == 0, unit
- * point strides; EWORKSPACE below hfta_conv1x1_bn_maxpool_bwd_workspace_bytes (256-byte aligned). */
+/* ------------------------------------------------------------------------
+ * The last per-point layer of a point-cloud model as ONE operator, forward and backward
+ * (fusion rules table rows "Conv1d" and "BatchNorm1d", the element-wise rows, then the max over
+ * points; section "Results" calls this workload memory-bound):
+ *     pooled[b,n,c] = max_l act( BatchNorm_c( sum_ci W[b,c,ci] X[b,n,ci,l] + bias[b,c] ) )
+ * The [Nb][B*Co][L] convolution output and its gradient are never formed, so no storage rounding
+ * happens inside the operator.  bf16 storage only.  Device pointers throughout.
+ *
+ * Forward.  X (strides xs, unit point stride), W:[B][Co][Ci], bias:[B][Co] or NULL, gamma/beta and the
+ * statistics arguments as in hfta_bn_fwd.  The batch statistics come from the moments of X
+ * (mean_c = W_c E[x] + bias_c, var_c = W_c Cov(x) W_c^T, Cov from a Ci x Ci Gram matrix accumulated
+ * in fp32 and combined in fp64); the maximum and its argmax from one pass of the matrix product.
+ * Outputs: V (storage dtype) and idx (int32), both with strides vs; save_mean, save_invstd; updated
+ * running statistics (if given); zhit fp32 [B][Nb][Co] = the convolution output at the argmax;
+ * saved_moments fp32, hfta_conv1x1_bn_maxpool_saved_floats(B, Ci, Co) floats, or NULL: what the
+ * backward can reuse (Gram matrix, sums of X, W times the Gram matrix).  idx is the first point
+ * that attains the maximum of the activated value up to fp32 rounding of the matrix product; among
+ * points whose activated values are equal (e.g. all clipped by a ReLU) any may be returned.
+ * act: NONE, RELU, or LEAKY with slope >= 0 (the argmax needs a non-decreasing activation).
+ *
+ * Backward.  Give exactly one of Z (the stored convolution output, strides zs, read ONLY at the
+ * Nb*Co argmax points) or zhit; saved_moments from the forward or NULL (then recomputed here).
+ * dV, idx, vs: pooled gradient and argmax.  Outputs dX (strides dxs, storage dtype), dW fp32
+ * [B][Co][Ci], dbias fp32 [B][Co] or NULL (exactly zero: a bias in front of a BatchNorm), dgamma,
+ * dbeta.  BatchNorm's backward is a per-channel affine map of z plus Nb spikes, so dX and dW reduce
+ * to the Gram matrix of X, a Ci -> Ci product with the spikes added in, and gathers at the argmax.
+ *
+ * EUNSUPPORTED unless bf16, Ci <= 128, Ci % 8 == 0, Co <= 1024, L % 4 == 0 and L < 2^21, 8-byte
+ * aligned X rows; EWORKSPACE below the *_workspace_bytes value (workspace 256-byte aligned; the
+ * workspace-size functions return 0 for unsupported shapes).
+ * ---------------------------------------------------------------------- */
+size_t hfta_conv1x1_bn_maxpool_saved_floats(int B, int Ci, int Co);
+size_t hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
+int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                                const void* X, const int64_t xs[4], const void* W, const void* bias,
+                                const float* gamma, const float* beta, float eps, float momentum,
+                                float* running_mean, float* running_var, float* save_mean, float* save_invstd,
+                                void* V, int32_t* idx, const int64_t vs[3], float* zhit, float* saved_moments,
+                                int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
 size_t hfta_conv1x1_bn_maxpool_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
 int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                                 const void* X, const int64_t xs[4], const void* W, const void* bias,
-                                const void* Z, const int64_t zs[4], const void* dV, const int32_t* idx,
-                                const int64_t vs[3], const float* gamma, const float* beta,
+                                const void* Z, const int64_t zs[4], const float* zhit, const float* saved_moments,
+                                const void* dV, const int32_t* idx, const int64_t vs[3],
+                                const float* gamma, const float* beta,
                                 const float* save_mean, const float* save_invstd,
                                 void* dX, const int64_t dxs[4], float* dW, float* dbias,
                                 float* dgamma, float* dbeta, int act, float act_slope,

@@ -141,13 +141,26 @@ class FusedPointNetCls(ParamArena):
         act = dict(dtype=self.tdt, device=self.dev)
         self.nconv = len(spec.conv) - 1
         self.nfc = len(spec.fc) - 1
-        self.z = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:]]
+        # The last per-point layer, its BatchNorm, ReLU and the max over points run as one operator,
+        # forward and backward, where the library supports the shape: its [Nb, B*C, L] output and the
+        # gradient of that tensor are then never allocated.
+        self.fused_tail = False
+        if fused_tail and self.nconv >= 2:
+            geo = (B, Nb, spec.conv[-2], spec.conv[-1], L, self.dt)
+            self.fused_tail_ws = max(hb.conv1x1_bn_maxpool_fwd_workspace_bytes(*geo),
+                                     hb.conv1x1_bn_maxpool_bwd_workspace_bytes(*geo))
+            self.fused_tail = hb.conv1x1_bn_maxpool_fwd_workspace_bytes(*geo) > 0
+        nz = self.nconv - 1 if self.fused_tail else self.nconv
+        self.z = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:1 + nz]]
         self.a = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:-1]]   # the last one is never stored
-        cmax = max(spec.conv[1:])
+        cmax = max(spec.conv[1:1 + nz])
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
         Cp = spec.conv[-1]
         self.pooled = torch.empty(B, Nb, Cp, **act)
         self.pool_idx = torch.empty(B, Nb, Cp, dtype=torch.int32, device=self.dev)
+        if self.fused_tail:
+            self.zhit = torch.empty(B, Nb, Cp, **f32)
+            self.tail_moments = torch.empty(hb.conv1x1_bn_maxpool_saved_floats(B, spec.conv[-2], Cp), **f32)
         self.fz = [torch.empty(B, Nb, f, **act) for f in spec.fc[1:]]
         self.fh = [torch.empty(B, Nb, f, **act) for f in spec.fc[1:-1]]
         self.fdrop = torch.empty(B, Nb, spec.fc[-2], **act) if spec.dropout_p > 0 else None
@@ -159,11 +172,8 @@ class FusedPointNetCls(ParamArena):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nfc):
             ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt))
-        # the last per-point layer's backward (max-pool, BatchNorm, both conv gradients) as one operator
-        # that never forms the dense [Nb, B*C, L] gradient, where the library supports the shape
-        self.fused_tail_ws = 0
-        if fused_tail and self.nconv >= 2:
-            self.fused_tail_ws = hb.conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, spec.conv[-2], spec.conv[-1], L, self.dt)
+        if not self.fused_tail:
+            self.fused_tail_ws = 0
         ws = max(ws, self.fused_tail_ws)
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
 
@@ -187,6 +197,18 @@ class FusedPointNetCls(ParamArena):
         for i in range(self.nconv):
             co = s.conv[i + 1]
             k = f"conv{i}"
+            if i == self.nconv - 1 and self.fused_tail:
+                vs = (Nb * co, co, 1)
+                hb.conv1x1_bn_maxpool_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
+                                          self.master(k + ".bn.g"), self.master(k + ".bn.b"), eps, mom,
+                                          self.running[k + ".bn.rm"], self.running[k + ".bn.rv"],
+                                          self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], self.pooled,
+                                          self.pool_idx, vs, self.zhit, self.tail_moments, hb.ACT_RELU, 0.0, self.ws)
+                P("conv1x1_bn_maxpool_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"),
+                  g=self.master(k + ".bn.g"), bt=self.master(k + ".bn.b"), v=self.pooled, idx=self.pool_idx,
+                  mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"], zhit=self.zhit)
+                ci = co
+                break
             hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
                            self.z[i], _cs(B, co, L))
             P("conv1x1_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
@@ -295,22 +317,22 @@ class FusedPointNetCls(ParamArena):
             ci, co = s.conv[i], s.conv[i + 1]
             k = f"conv{i}"
             cs = _cs(B, co, L)
-            dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
-            if i == self.nconv - 1 and self.fused_tail_ws > 0:
+            if i == self.nconv - 1 and self.fused_tail:
                 xin, dxin = self.a[i - 1], self.dbuf[cur][:Nb * B * ci * L]
                 hb.conv1x1_bn_maxpool_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
-                                          self.z[i], cs, dpool, self.pool_idx, (Nb * co, co, 1),
-                                          self.master(k + ".bn.g"), self.master(k + ".bn.b"),
+                                          None, None, self.zhit, self.tail_moments, dpool, self.pool_idx,
+                                          (Nb * co, co, 1), self.master(k + ".bn.g"), self.master(k + ".bn.b"),
                                           self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], dxin,
                                           _cs(B, ci, L), self.g(k + ".w"), self.g(k + ".b"), self.g(k + ".bn.g"),
                                           self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.ws)
-                P("conv1x1_bn_maxpool_bwd", layer=k, x=xin, w=self.w(k + ".w"), z=self.z[i],
+                P("conv1x1_bn_maxpool_bwd", layer=k, x=xin, w=self.w(k + ".w"), b=self.w(k + ".b"),
                   dv=dpool.view(B, Nb, co), idx=self.pool_idx, g=self.master(k + ".bn.g"),
-                  b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
+                  bt=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
                   dx=dxin.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"), dg=self.g(k + ".bn.g"),
                   dbt=self.g(k + ".bn.b"))
                 da = dxin
                 continue
+            dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
             if i == self.nconv - 1:
                 hb.bn_bwd_maxpool(B, Nb, co, L, dt, self.z[i], cs, dpool, self.pool_idx, (Nb * co, co, 1),
                                   self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],

@@ -57,7 +57,10 @@ _SIGS = {
     "hfta_bn_fwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
-    "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 19 + [_i, _f, _p, _sz, _p]),
+    "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 21 + [_i, _f, _p, _sz, _p]),
+    "hfta_conv1x1_bn_maxpool_saved_floats": (_sz, [_i] * 3),
+    "hfta_conv1x1_bn_maxpool_fwd_workspace_bytes": (_sz, [_i] * 6),
+    "hfta_conv1x1_bn_maxpool_fwd": (_i, [_i] * 6 + [_p] * 6 + [_f, _f] + [_p] * 9 + [_i, _f, _p, _sz, _p]),
     "hfta_maxpool_points": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p]),
     "hfta_maxpool_points_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _s4, _p, _s4, _p]),
     "hfta_adam_step": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
@@ -220,15 +223,35 @@ def conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype) -> int:
     return _lib.hfta_conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype)
 
 
-def conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, dV, idx, vs, gamma, beta, save_mean,
-                           save_invstd, dX, dxs, dW, dbias, dgamma, dbeta, act=ACT_NONE, act_slope=0.0,
+def conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, zhit, saved_moments, dV, idx, vs, gamma, beta,
+                           save_mean, save_invstd, dX, dxs, dW, dbias, dgamma, dbeta, act=ACT_NONE, act_slope=0.0,
                            workspace=None, stream=None):
     wp, wb = _ws(workspace)
     _check(_lib.hfta_conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(bias),
-                                            _ptr(Z), _strides(zs), _ptr(dV), _ptr(idx), _strides(vs, 3), _ptr(gamma),
+                                            _ptr(Z), None if zs is None else _strides(zs), _ptr(zhit),
+                                            _ptr(saved_moments), _ptr(dV), _ptr(idx), _strides(vs, 3), _ptr(gamma),
                                             _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dX), _strides(dxs),
                                             _ptr(dW), _ptr(dbias), _ptr(dgamma), _ptr(dbeta), act, act_slope, wp, wb,
                                             _stream(stream)), "hfta_conv1x1_bn_maxpool_bwd")
+
+
+def conv1x1_bn_maxpool_saved_floats(B, Ci, Co):
+    return _lib.hfta_conv1x1_bn_maxpool_saved_floats(B, Ci, Co)
+
+
+def conv1x1_bn_maxpool_fwd_workspace_bytes(B, Nb, Ci, Co, L, dtype):
+    return _lib.hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(B, Nb, Ci, Co, L, dtype)
+
+
+def conv1x1_bn_maxpool_fwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, gamma, beta, eps, momentum, running_mean, running_var,
+                           save_mean, save_invstd, V, idx, vs, zhit, saved_moments, act=ACT_NONE, act_slope=0.0,
+                           workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_conv1x1_bn_maxpool_fwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(bias),
+                                            _ptr(gamma), _ptr(beta), eps, momentum, _ptr(running_mean),
+                                            _ptr(running_var), _ptr(save_mean), _ptr(save_invstd), _ptr(V), _ptr(idx),
+                                            _strides(vs, 3), _ptr(zhit), _ptr(saved_moments), act, act_slope, wp, wb,
+                                            _stream(stream)), "hfta_conv1x1_bn_maxpool_fwd")
 
 
 def maxpool_points(B, Nb, C_, L, dtype, X, xs, V, idx, vs, stream=None):

@@ -27,6 +27,8 @@ struct CbpChan { float a, dbeta, dgamma, invstd, mean, bias; };
 struct CbpArgs {
   const bf16_raw* X; const bf16_raw* W; const bf16_raw* bias; const bf16_raw* Z; const bf16_raw* dV;
   const int32_t* idx;
+  const float* zhit;  // [B][Nb][Co] convolution output at the argmax (then Z is not read), or null
+  const float* Tin;   // [B][Co][Ci] W XX from the forward operator, or null: computed here
   const float* gamma; const float* beta; const float* save_mean; const float* save_invstd;
   bf16_raw* dX; float* dW; float* dbias; float* dgamma; float* dbeta;
   int64_t xsb, xsn, xsc, zsb, zsn, zsc, vsb, vsn, vsc, dxsb, dxsn, dxsc;
@@ -58,7 +60,8 @@ __global__ __launch_bounds__(64) void cbp_coef_kernel(CbpArgs p) {
   float s1 = 0.f, s2 = 0.f;
   for (int n = lane; n < p.Nb; n += 64) {
     const int hit = min(max(p.idx[b * p.vsb + n * p.vsn + c * p.vsc], 0), p.L - 1);
-    const float z = bf16_to_f32(p.Z[b * p.zsb + n * p.zsn + c * p.zsc + hit]);
+    const float z = p.zhit ? p.zhit[((int64_t)b * p.Nb + n) * p.Co + c]
+                           : bf16_to_f32(p.Z[b * p.zsb + n * p.zsn + c * p.zsc + hit]);
     const float xh = (z - mean) * invstd;
     const float gr = bf16_to_f32(p.dV[b * p.vsb + n * p.vsn + c * p.vsc]) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
     s1 += gr;
@@ -327,7 +330,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void cbp_dx_kernel(CbpArgs p) {
   }
   __syncthreads();                                       // both tiles are dead from here on
 
-  if (t < 128 && t < p.Ci) p.SXpart[((int64_t)bz * gridDim.x + bx) * p.Ci + t] = sxs[t] + sxs[t + 128];
+  if (p.SXpart && t < 128 && t < p.Ci) p.SXpart[((int64_t)bz * gridDim.x + bx) * p.Ci + t] = sxs[t] + sxs[t + 128];
   bf16_raw* dXb = p.dX + b * p.dxsb + n * p.dxsn;
   float* stage = reinterpret_cast<float*>(Gs);
   unsigned char* Wh = Xs;
@@ -430,22 +433,22 @@ __global__ __launch_bounds__(GEMM_THREADS) void cbp_dx_kernel(CbpArgs p) {
 }
 
 // ---- SX[b][ci] = sum over (n, l) of x, from the per-tile sums, in a fixed order -----------------
-__global__ __launch_bounds__(1024) void cbp_sx_kernel(CbpArgs p, int parts) {
+__global__ __launch_bounds__(1024) void cbp_sx_kernel(const float* part, float* SX, int Ci, int parts) {
   __shared__ float red[64][16];
   const int b = blockIdx.y, cl = threadIdx.x & 15, g = threadIdx.x >> 4;
   const int ci = blockIdx.x * 16 + cl;
-  const float* src = p.SXpart + (int64_t)b * parts * p.Ci;
+  const float* src = part + (int64_t)b * parts * Ci;
   float s = 0.f;
-  if (ci < p.Ci) {
+  if (ci < Ci) {
 #pragma unroll 4
-    for (int q = g; q < parts; q += 64) s += src[(int64_t)q * p.Ci + ci];
+    for (int q = g; q < parts; q += 64) s += src[(int64_t)q * Ci + ci];
   }
   red[g][cl] = s;
   __syncthreads();
-  if (g == 0 && ci < p.Ci) {
+  if (g == 0 && ci < Ci) {
     float tot = 0.f;
     for (int k = 0; k < 64; ++k) tot += red[k][cl];
-    p.SX[(int64_t)b * p.Ci + ci] = tot;
+    SX[(int64_t)b * Ci + ci] = tot;
   }
 }
 
@@ -464,11 +467,17 @@ __global__ __launch_bounds__(128) void cbp_dw_kernel(CbpArgs p) {
   float T[CB];
 #pragma unroll
   for (int e = 0; e < CB; ++e) T[e] = 0.f;
-#pragma unroll 8
-  for (int ci = 0; ci < p.Ci; ++ci) {                    // Ci is a multiple of 8 (host)
-    const float x = XXb[(int64_t)ci * p.Ci + cj];
+  if (p.Tin) {
 #pragma unroll
-    for (int e = 0; e < CB; ++e) T[e] = fmaf(wrow[e][ci], x, T[e]);
+    for (int e = 0; e < CB; ++e)
+      if (c0 + e < p.Co) T[e] = p.Tin[((int64_t)b * p.Co + c0 + e) * p.Ci + cj];
+  } else {
+#pragma unroll 8
+    for (int ci = 0; ci < p.Ci; ++ci) {                  // Ci is a multiple of 8 (host)
+      const float x = XXb[(int64_t)ci * p.Ci + cj];
+#pragma unroll
+      for (int e = 0; e < CB; ++e) T[e] = fmaf(wrow[e][ci], x, T[e]);
+    }
   }
   const double m = (double)p.Nb * (double)p.L;
   const double sx = (double)p.SX[(int64_t)b * p.Ci + cj], ex = sx / m;
@@ -491,6 +500,301 @@ __global__ __launch_bounds__(128) void cbp_dw_kernel(CbpArgs p) {
 
 size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// =====================================================================================================
+// Forward of the same operator:  pooled = max_l act(BatchNorm(W x + bias)),  its argmax, the
+// BatchNorm statistics -- without forming the [Nb, B*Co, L] convolution output.
+//   * statistics from the input's moments: mean_c = (W_c SX)/m + bias_c,
+//     var_c = (W_c XX W_c^T)/m - ((W_c SX)/m)^2, with XX, SX as in the backward (fp32 Gram matrix,
+//     combined in double);
+//   * the activations handled here (none, ReLU, LeakyReLU with slope >= 0) are non-decreasing and
+//     BatchNorm is increasing in z where gamma > 0 and decreasing where gamma < 0, so the argmax of
+//     the activated value is the argmax of  sign(gamma_c) (W_c x):  one pass of the matrix product
+//     with sign-folded weights, a running (max, first argmax) per channel and tile, nothing stored.
+// =====================================================================================================
+struct FbpArgs {
+  const bf16_raw* X; const bf16_raw* W; const bf16_raw* bias;
+  const float* gamma; const float* beta;
+  float* running_mean; float* running_var; float* save_mean; float* save_invstd;
+  bf16_raw* V; int32_t* idx; float* zhit;
+  int64_t xsb, xsn, xsc, vsb, vsn, vsc;
+  int B, Nb, Ci, Co, L, act, tiles_co;
+  float slope, eps, momentum;
+  float* XX; float* SX; float* T;          // [B][Ci][Ci], [B][Ci], [B][Co][Ci]
+  float* SXpart;                           // [B][Nb][tiles][2][Ci]
+  float* pmax; int* pidx;                  // [B][Nb][tiles][Co]
+  uint32_t x_extent, w_extent;
+};
+
+// One workgroup owns a 128-point slice of one sample: the X tile (transposed) stays in LDS, the
+// loop walks the 128-row tiles of W (next tile in flight in registers), and the epilogue of a
+// step is a per-lane scan of the accumulators for (max, first argmax) instead of a store.
+template <int KT>
+__global__ __launch_bounds__(GEMM_THREADS) void fbp_main_kernel(FbpArgs p) {
+  constexpr int PITCH = KT * 2 + 16;
+  constexpr int TILE = 128 * PITCH;
+  constexpr int SUB = KT / 32;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE];
+  __shared__ float pm_v[2][2][128];                    // [step parity][point half][channel]
+  __shared__ int pm_p[2][2][128];
+  unsigned char* Xs = smem;
+  unsigned char* Ws = smem + TILE;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int bx = blockIdx.x, bz = blockIdx.z;
+  {  // XCD-aware renumbering (see gemm_kernel)
+    const int total = gridDim.x * gridDim.z, per = total >> 3;
+    const int lin = blockIdx.x + gridDim.x * blockIdx.z;
+    if (lin < (per << 3)) {
+      const int l2 = (lin & 7) * per + (lin >> 3);
+      bz = l2 / gridDim.x;
+      bx = l2 - bz * gridDim.x;
+    }
+  }
+  const int b = bz / p.Nb, n = bz % p.Nb;
+  const int l0 = bx * 128;
+  const __amdgpu_buffer_rsrc_t rw = pf_rsrc(p.W + (int64_t)b * p.Co * p.Ci, p.w_extent);
+  const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + b * p.xsb + n * p.xsn, p.x_extent);
+  const float* gam = p.gamma + (int64_t)b * p.Co;
+
+  {  // X tile, transposed in registers into [point][ci]
+    const int kq = t % 8, ng = t / 8;
+    const int c = l0 + ng * 4;
+    const uint32_t ldb = (uint32_t)(p.xsc * 2);
+    uint2 q[SUB][4];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = s * 32 + 4 * kq + j;
+        const bool ok = k < p.Ci && c + 4 <= p.L;
+        const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? (uint32_t)k * ldb + (uint32_t)c * 2u : PF_OOB), 0, 0);
+        q[s][j] = make_uint2(v.x, v.y);
+      }
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) {
+      const uint32_t a0 = q[s][0].x, a1 = q[s][1].x, a2 = q[s][2].x, a3 = q[s][3].x;
+      const uint32_t b0 = q[s][0].y, b1 = q[s][1].y, b2 = q[s][2].y, b3 = q[s][3].y;
+      uint2 o[4];
+      o[0] = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
+      o[1] = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
+      o[2] = make_uint2((b0 & 0xffffu) | (b1 << 16), (b2 & 0xffffu) | (b3 << 16));
+      o[3] = make_uint2((b0 >> 16) | (b1 & 0xffff0000u), (b2 >> 16) | (b3 & 0xffff0000u));
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<uint2*>(Xs + (ng * 4 + i) * PITCH + s * 64 + kq * 8) = o[i];
+    }
+  }
+
+  // W tiles: rows t/4 and t/4+64, 16-byte group t%4 of every 32-wide k block; a row whose gamma is
+  // negative gets the sign bit of every element flipped (exact), so that every channel looks for a maximum
+  const int wr = t >> 2, wg = (t & 3) * 8;
+  uint4 wq[SUB][2];
+  uint32_t flip[2];
+  auto load_w = [&](int ct) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int row = ct * 128 + wr + 64 * h;
+      flip[h] = (row < p.Co && gam[row] < 0.f) ? 0x80008000u : 0u;
+#pragma unroll
+      for (int s = 0; s < SUB; ++s) {
+        const int k = s * 32 + wg;
+        const bool ok = row < p.Co && k + 8 <= p.Ci;
+        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(ok ? ((uint32_t)row * (uint32_t)p.Ci + (uint32_t)k) * 2u : PF_OOB), 0, 0);
+        wq[s][h] = make_uint4(v.x, v.y, v.z, v.w);
+      }
+    }
+  };
+  load_w(0);
+
+  const int r = lane & 31, gsel = lane >> 5;
+  const int tiles = gridDim.x;
+  float* pmax = p.pmax + ((int64_t)bz * tiles + bx) * p.Co;
+  int* pidx = p.pidx + ((int64_t)bz * tiles + bx) * p.Co;
+  const int lim = p.L - l0;                              // points of this slice that exist (>= 1)
+  auto publish = [&](int ct) {                           // step ct's per-channel result, both point halves merged
+    if (t < 128 && ct * 128 + t < p.Co) {
+      const int pb = ct & 1;
+      const float v0 = pm_v[pb][0][t], v1 = pm_v[pb][1][t];
+      const bool hi = v1 > v0;                           // a tie goes to the lower points
+      pmax[ct * 128 + t] = hi ? v1 : v0;
+      pidx[ct * 128 + t] = l0 + (hi ? pm_p[pb][1][t] : pm_p[pb][0][t]);
+    }
+  };
+
+  for (int ct = 0; ct < p.tiles_co; ++ct) {
+#pragma unroll
+    for (int s = 0; s < SUB; ++s)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint4 w = wq[s][h];
+        *reinterpret_cast<uint4*>(Ws + (wr + 64 * h) * PITCH + (s * 32 + wg) * 2) =
+            make_uint4(w.x ^ flip[h], w.y ^ flip[h], w.z ^ flip[h], w.w ^ flip[h]);
+      }
+    __syncthreads();
+    load_w(ct + 1);                      // past the last tile: rows >= Co, zeros, no traffic
+    if (ct == 0) {                       // this slice's part of sum_l x: thread (ci, half) adds 64 points in order
+      const int ci = t & 127, half = t >> 7;
+      if (ci < p.Ci) {
+        float sx = 0.f;
+        const unsigned char* col = Xs + (half * 64) * PITCH + ci * 2;
+#pragma unroll 8
+        for (int q = 0; q < 64; ++q) sx += bf16_to_f32(*reinterpret_cast<const bf16_raw*>(col + q * PITCH));
+        p.SXpart[(((int64_t)bz * tiles + bx) * 2 + half) * p.Ci + ci] = sx;
+      }
+    } else {
+      publish(ct - 1);
+    }
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KT / 16; ++s) {
+      bf16x8_t a[2], bb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[i] = *reinterpret_cast<const bf16x8_t*>(Ws + (wm * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
+        bb[i] = *reinterpret_cast<const bf16x8_t*>(Xs + (wn * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j], a[i], acc[i][j], 0, 0, 0);
+    }
+    // lane = channel wm*64 + i*32 + (lane & 31); its 32 points wn*64 + j*32 + 8q + 4(lane>>5) + e in rising order
+    float bv[2];
+    int bp[2];
+    const int pt0 = wn * 64 + 4 * gsel;
+    if (lim >= 128) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        bv[i] = -INFINITY; bp[i] = 0;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float val = acc[i][j][v];
+            const int pt = pt0 + j * 32 + 8 * (v >> 2) + (v & 3);
+            if (val > bv[i]) { bv[i] = val; bp[i] = pt; }
+          }
+      }
+    } else {                             // the last slice: points past L do not take part
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        bv[i] = -INFINITY; bp[i] = 0;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int pt = pt0 + j * 32 + 8 * (v >> 2) + (v & 3);
+            const float val = pt < lim ? acc[i][j][v] : -INFINITY;
+            if (val > bv[i]) { bv[i] = val; bp[i] = pt; }
+          }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {        // the two lane halves hold interleaved groups of four points
+      const float ov = __shfl_xor(bv[i], 32, 64);
+      const int op = __shfl_xor(bp[i], 32, 64);
+      if (ov > bv[i] || (ov == bv[i] && op < bp[i])) { bv[i] = ov; bp[i] = op; }
+      if (lane < 32) {
+        pm_v[ct & 1][wn][wm * 64 + i * 32 + lane] = bv[i];
+        pm_p[ct & 1][wn][wm * 64 + i * 32 + lane] = bp[i];
+      }
+    }
+    __syncthreads();                     // every wavefront is done with the W tile; step ct's maxima are in LDS
+  }
+  publish(p.tiles_co - 1);
+}
+
+// ---- statistics from the moments; T = W XX kept for the backward operator --------------------------
+__global__ __launch_bounds__(128) void fbp_stats_kernel(FbpArgs p) {
+  constexpr int CB = 8;
+  __shared__ float wrow[CB][128];
+  __shared__ double red[2][CB][2];
+  const int c0 = blockIdx.x * CB, b = blockIdx.y, cj = threadIdx.x;
+  for (int e = cj; e < CB * p.Ci; e += 128) {
+    const int cc = e / p.Ci, k = e - cc * p.Ci;
+    wrow[cc][k] = c0 + cc < p.Co ? bf16_to_f32(p.W[((int64_t)b * p.Co + c0 + cc) * p.Ci + k]) : 0.f;
+  }
+  __syncthreads();
+  const bool live = cj < p.Ci;
+  const float* XXb = p.XX + (int64_t)b * p.Ci * p.Ci;
+  double T[CB];
+#pragma unroll
+  for (int e = 0; e < CB; ++e) T[e] = 0.0;
+  if (live) {
+#pragma unroll 8
+    for (int ci = 0; ci < p.Ci; ++ci) {                  // Ci is a multiple of 8 (host)
+      const double x = (double)XXb[(int64_t)ci * p.Ci + cj];
+#pragma unroll
+      for (int e = 0; e < CB; ++e) T[e] = fma((double)wrow[e][ci], x, T[e]);
+    }
+  }
+  const double sxj = live ? (double)p.SX[(int64_t)b * p.Ci + cj] : 0.0;
+#pragma unroll
+  for (int e = 0; e < CB; ++e) {
+    if (live && c0 + e < p.Co) p.T[((int64_t)b * p.Co + c0 + e) * p.Ci + cj] = (float)T[e];
+    const double w = live ? (double)wrow[e][cj] : 0.0;
+    double q = T[e] * w, s1 = w * sxj;                   // terms of W_c XX W_c^T and of W_c SX
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { q += __shfl_xor(q, o, 64); s1 += __shfl_xor(s1, o, 64); }
+    if ((cj & 63) == 0) { red[cj >> 6][e][0] = q; red[cj >> 6][e][1] = s1; }
+  }
+  __syncthreads();
+  if (cj < CB && c0 + cj < p.Co) {
+    const int k = b * p.Co + c0 + cj;
+    const double m = (double)p.Nb * (double)p.L;
+    const double quad = red[0][cj][0] + red[1][cj][0], ws = red[0][cj][1] + red[1][cj][1];
+    const double mz = ws / m;                            // mean of W x (the bias shifts the mean only)
+    double var = quad / m - mz * mz;
+    var = var < 0.0 ? 0.0 : var;
+    const float mean = (float)(mz + (p.bias ? (double)bf16_to_f32(p.bias[k]) : 0.0));
+    const float varf = (float)var;
+    p.save_mean[k] = mean;
+    p.save_invstd[k] = (float)(1.0 / sqrt(var + (double)p.eps));
+    if (p.running_mean) {
+      const float mf = (float)m;
+      const float unb = mf > 1.f ? varf * (mf / (mf - 1.f)) : varf;
+      p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
+      p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
+    }
+  }
+}
+
+// ---- per (model, sample, channel): first maximum over the slices, then BatchNorm + activation ------
+__global__ __launch_bounds__(256) void fbp_finish_kernel(FbpArgs p, int tiles) {
+  const int c = blockIdx.x * 256 + threadIdx.x, n = blockIdx.y, b = blockIdx.z;
+  if (c >= p.Co) return;
+  const int64_t bn = (int64_t)b * p.Nb + n;
+  const float* pv = p.pmax + bn * tiles * p.Co + c;
+  const int* pi = p.pidx + bn * tiles * p.Co + c;
+  float best = pv[0];
+  int at = pi[0];
+  for (int q = 1; q < tiles; ++q) {
+    const float v = pv[(int64_t)q * p.Co];
+    if (v > best) { best = v; at = pi[(int64_t)q * p.Co]; }
+  }
+  const int k = b * p.Co + c;
+  const float g = p.gamma[k];
+  const float z = (g < 0.f ? -best : best) + (p.bias ? bf16_to_f32(p.bias[k]) : 0.f);
+  const float y = apply_act(fmaf(g * p.save_invstd[k], z - p.save_mean[k], p.beta[k]), p.act, p.slope);
+  p.V[b * p.vsb + n * p.vsn + c * p.vsc] = f32_to_bf16(y);
+  p.idx[b * p.vsb + n * p.vsn + c * p.vsc] = at;
+  p.zhit[bn * p.Co + c] = z;
+}
+
+struct FbpLayout { size_t SXpart, pmax, pidx, moments, part, total; };
+
+size_t saved_floats(int B, int Ci, int Co) { return (size_t)B * ((size_t)Ci * Ci + Ci + (size_t)Co * Ci); }
+
+
 struct CbpLayout { size_t chan, p0, p1, s, XX, SX, negG, v, xg, SXpart, skey, sval, toff, part, total; };
 
 GemmDesc gram_desc(int B, int Nb, int Ci, int L, const void* X, const int64_t xs[4], float* XX) {
@@ -502,6 +806,22 @@ GemmDesc gram_desc(int B, int Nb, int Ci, int L, const void* X, const int64_t xs
   d.c_ld = Ci; d.c_g0 = (int64_t)Ci * Ci;
   d.act = HFTA_ACT_NONE; d.dtype = HFTA_BF16; d.out_f32 = true; d.splits = 1;
   return d;
+}
+
+FbpLayout fbp_layout(int B, int Nb, int Ci, int Co, int L, bool own_moments) {
+  FbpLayout w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += a256(bytes); return o; };
+  const size_t tiles = (size_t)(L + 127) / 128;
+  w.SXpart = take((size_t)B * Nb * tiles * 2 * Ci * 4);
+  w.pmax = take((size_t)B * Nb * tiles * Co * 4);
+  w.pidx = take((size_t)B * Nb * tiles * Co * 4);
+  w.moments = take(own_moments ? saved_floats(B, Ci, Co) * 4 : 0);
+  const int64_t unit[4] = {(int64_t)Ci * L, (int64_t)B * Ci * L, L, 1};
+  GemmDesc d = gram_desc(B, Nb, Ci, L, nullptr, unit, nullptr);
+  w.part = take(gemm_partial_bytes(d, gemm_pick_splits(d)));
+  w.total = off;
+  return w;
 }
 
 CbpLayout cbp_layout(int B, int Nb, int Ci, int Co, int L) {
@@ -543,16 +863,17 @@ size_t hfta_conv1x1_bn_maxpool_bwd_workspace_bytes(int B, int Nb, int Ci, int Co
 }
 
 int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
-                                const void* W, const void* bias, const void* Z, const int64_t zs[4], const void* dV,
-                                const int32_t* idx, const int64_t vs[3], const float* gamma, const float* beta,
-                                const float* save_mean, const float* save_invstd, void* dX, const int64_t dxs[4],
-                                float* dW, float* dbias, float* dgamma, float* dbeta, int act, float act_slope,
-                                void* workspace, size_t ws_bytes, void* stream) {
-  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !W || !Z || !zs || !dV ||
+                                const void* W, const void* bias, const void* Z, const int64_t zs[4], const float* zhit,
+                                const float* saved_moments, const void* dV, const int32_t* idx, const int64_t vs[3],
+                                const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
+                                void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
+                                int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !W || !dV ||
       !idx || !vs || !gamma || !beta || !save_mean || !save_invstd || !dX || !dxs || !dW || !dgamma || !dbeta)
     return HFTA_EINVAL;
+  if ((Z == nullptr) == (zhit == nullptr) || (Z && !zs)) return HFTA_EINVAL;     // exactly one source of z at the argmax
   if (!(act == HFTA_ACT_NONE || act == HFTA_ACT_RELU || act == HFTA_ACT_LEAKY)) return HFTA_EUNSUPPORTED;
-  if (!cbp_supported(B, Nb, Ci, Co, L, dtype) || xs[3] != 1 || zs[3] != 1 || dxs[3] != 1) return HFTA_EUNSUPPORTED;
+  if (!cbp_supported(B, Nb, Ci, Co, L, dtype) || xs[3] != 1 || (Z && zs[3] != 1) || dxs[3] != 1) return HFTA_EUNSUPPORTED;
   auto al = [](const void* q, size_t a) { return (reinterpret_cast<uintptr_t>(q) % a) == 0; };
   if (!al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0 || !al(W, 4)) return HFTA_EUNSUPPORTED;
   const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2;
@@ -564,10 +885,11 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
 
   CbpArgs a{};
   a.X = (const bf16_raw*)X; a.W = (const bf16_raw*)W; a.bias = (const bf16_raw*)bias; a.Z = (const bf16_raw*)Z;
-  a.dV = (const bf16_raw*)dV; a.idx = idx;
+  a.dV = (const bf16_raw*)dV; a.idx = idx; a.zhit = zhit;
   a.gamma = gamma; a.beta = beta; a.save_mean = save_mean; a.save_invstd = save_invstd;
   a.dX = (bf16_raw*)dX; a.dW = dW; a.dbias = dbias; a.dgamma = dgamma; a.dbeta = dbeta;
-  a.xsb = xs[0]; a.xsn = xs[1]; a.xsc = xs[2]; a.zsb = zs[0]; a.zsn = zs[1]; a.zsc = zs[2];
+  a.xsb = xs[0]; a.xsn = xs[1]; a.xsc = xs[2];
+  if (Z) { a.zsb = zs[0]; a.zsn = zs[1]; a.zsc = zs[2]; }
   a.vsb = vs[0]; a.vsn = vs[1]; a.vsc = vs[2]; a.dxsb = dxs[0]; a.dxsn = dxs[1]; a.dxsc = dxs[2];
   a.B = B; a.Nb = Nb; a.Ci = Ci; a.Co = Co; a.L = L; a.act = act; a.slope = act_slope;
   a.chan = (CbpChan*)(ws + lay.chan); a.p0 = (float*)(ws + lay.p0); a.p1 = (float*)(ws + lay.p1);
@@ -577,14 +899,21 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   a.c_vec = (al(dX, 8) && dxs[0] % 4 == 0 && dxs[1] % 4 == 0 && dxs[2] % 4 == 0) ? 8 : 0;
   a.x_extent = (uint32_t)x_ext; a.g_extent = (uint32_t)((int64_t)Ci * Ci * 2);
 
+  if (saved_moments) {           // XX, SX and T = W XX as the forward operator left them
+    a.XX = const_cast<float*>(saved_moments);
+    a.SX = a.XX + (size_t)B * Ci * Ci;
+    a.Tin = a.SX + (size_t)B * Ci;
+    a.SXpart = nullptr;
+  }
   hipLaunchKernelGGL(cbp_coef_kernel, dim3((unsigned)Co, (unsigned)B), dim3(64), 0, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
-  // Gram matrix of the layer input: XX[b] = sum_{n,l} x x^T, through the batched GEMM core
-  GemmDesc g = gram_desc(B, Nb, Ci, L, X, xs, a.XX);
-  g.splits = gemm_pick_splits(g);
-  g.partial = (float*)(ws + lay.part);
-  int rc = gemm_launch(g, st);
-  if (rc != HFTA_OK) return rc;
+  if (!saved_moments) {          // Gram matrix of the layer input: XX[b] = sum_{n,l} x x^T, through the batched GEMM core
+    GemmDesc g = gram_desc(B, Nb, Ci, L, X, xs, a.XX);
+    g.splits = gemm_pick_splits(g);
+    g.partial = (float*)(ws + lay.part);
+    const int rc = gemm_launch(g, st);
+    if (rc != HFTA_OK) return rc;
+  }
   const int T32 = (Ci + 31) / 32;
   hipLaunchKernelGGL(cbp_gram_w_kernel, dim3((unsigned)(T32 * T32), (unsigned)B), dim3(GW_WAVES * 64), 0, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
@@ -595,8 +924,73 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   if (Ci <= 64) hipLaunchKernelGGL(cbp_dx_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
   else hipLaunchKernelGGL(cbp_dx_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
-  hipLaunchKernelGGL(cbp_sx_kernel, dim3((unsigned)((Ci + 15) / 16), (unsigned)B), dim3(1024), 0, st, a, Nb * (int)grid.x);
+  if (!saved_moments)
+    hipLaunchKernelGGL(cbp_sx_kernel, dim3((unsigned)((Ci + 15) / 16), (unsigned)B), dim3(1024), 0, st, a.SXpart, a.SX, Ci,
+                       Nb * (int)grid.x);
   hipLaunchKernelGGL(cbp_dw_kernel, dim3((unsigned)((Co + 7) / 8), (unsigned)B), dim3(128), 0, st, a);
+  return launch_status();
+}
+
+size_t hfta_conv1x1_bn_maxpool_saved_floats(int B, int Ci, int Co) {
+  if (B <= 0 || Ci <= 0 || Co <= 0) return 0;
+  return saved_floats(B, Ci, Co);
+}
+
+size_t hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  if (!cbp_supported(B, Nb, Ci, Co, L, dtype)) return 0;
+  return fbp_layout(B, Nb, Ci, Co, L, true).total;
+}
+
+int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                                const void* W, const void* bias, const float* gamma, const float* beta, float eps,
+                                float momentum, float* running_mean, float* running_var, float* save_mean,
+                                float* save_invstd, void* V, int32_t* idx, const int64_t vs[3], float* zhit,
+                                float* saved_moments, int act, float act_slope, void* workspace, size_t ws_bytes,
+                                void* stream) {
+  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !W || !gamma || !beta ||
+      !save_mean || !save_invstd || !V || !idx || !vs || !zhit || !(eps >= 0.f))
+    return HFTA_EINVAL;
+  if ((running_mean == nullptr) != (running_var == nullptr)) return HFTA_EINVAL;
+  // the argmax is taken on sign(gamma) z: needs a non-decreasing activation
+  if (!(act == HFTA_ACT_NONE || act == HFTA_ACT_RELU || (act == HFTA_ACT_LEAKY && act_slope >= 0.f))) return HFTA_EUNSUPPORTED;
+  if (!cbp_supported(B, Nb, Ci, Co, L, dtype) || xs[3] != 1) return HFTA_EUNSUPPORTED;
+  auto al = [](const void* q, size_t a) { return (reinterpret_cast<uintptr_t>(q) % a) == 0; };
+  if (!al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0 || !al(W, 16)) return HFTA_EUNSUPPORTED;
+  const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2, w_ext = (int64_t)Co * Ci * 2;
+  if (x_ext >= (int64_t)1 << 31 || w_ext >= (int64_t)1 << 31) return HFTA_EUNSUPPORTED;
+  const FbpLayout lay = fbp_layout(B, Nb, Ci, Co, L, true);
+  if (!workspace || !al(workspace, 256) || ws_bytes < lay.total) return HFTA_EWORKSPACE;
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  hipStream_t st = as_stream(stream);
+
+  FbpArgs a{};
+  a.X = (const bf16_raw*)X; a.W = (const bf16_raw*)W; a.bias = (const bf16_raw*)bias; a.gamma = gamma; a.beta = beta;
+  a.running_mean = running_mean; a.running_var = running_var; a.save_mean = save_mean; a.save_invstd = save_invstd;
+  a.V = (bf16_raw*)V; a.idx = idx; a.zhit = zhit;
+  a.xsb = xs[0]; a.xsn = xs[1]; a.xsc = xs[2]; a.vsb = vs[0]; a.vsn = vs[1]; a.vsc = vs[2];
+  a.B = B; a.Nb = Nb; a.Ci = Ci; a.Co = Co; a.L = L; a.act = act; a.tiles_co = (Co + 127) / 128;
+  a.slope = act_slope; a.eps = eps; a.momentum = momentum;
+  a.XX = saved_moments ? saved_moments : (float*)(ws + lay.moments);
+  a.SX = a.XX + (size_t)B * Ci * Ci;
+  a.T = a.SX + (size_t)B * Ci;
+  a.SXpart = (float*)(ws + lay.SXpart); a.pmax = (float*)(ws + lay.pmax); a.pidx = (int*)(ws + lay.pidx);
+  a.x_extent = (uint32_t)x_ext; a.w_extent = (uint32_t)w_ext;
+
+  GemmDesc g = gram_desc(B, Nb, Ci, L, X, xs, a.XX);
+  g.splits = gemm_pick_splits(g);
+  g.partial = (float*)(ws + lay.part);
+  const int rc = gemm_launch(g, st);
+  if (rc != HFTA_OK) return rc;
+  dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
+  if (Ci <= 64) hipLaunchKernelGGL(fbp_main_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
+  else hipLaunchKernelGGL(fbp_main_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  hipLaunchKernelGGL(cbp_sx_kernel, dim3((unsigned)((Ci + 15) / 16), (unsigned)B), dim3(1024), 0, st, a.SXpart, a.SX, Ci,
+                     Nb * (int)grid.x * 2);
+  hipLaunchKernelGGL(fbp_stats_kernel, dim3((unsigned)((Co + 7) / 8), (unsigned)B), dim3(128), 0, st, a);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  hipLaunchKernelGGL(fbp_finish_kernel, dim3((unsigned)((Co + 255) / 256), (unsigned)Nb, (unsigned)B), dim3(256), 0, st, a,
+                     (int)grid.x);
   return launch_status();
 }
 

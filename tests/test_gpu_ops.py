@@ -558,8 +558,8 @@ def test_conv1x1_bn_maxpool_bwd_fused(hb, B, Nb, Ci, Co, L, act):
     nws = hb.conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype])
     assert nws > 0
     ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
-    hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bi, Z, sz, dV, I, vs, G, Bt, SM, SI, dX, sx, dW,
-                              dB0, dG, dBt, act, slope, ws)
+    hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bi, Z, sz, None, None, dV, I, vs, G, Bt, SM, SI, dX,
+                              sx, dW, dB0, dG, dBt, act, slope, ws)
     sc = np.abs(dv).sum(axis=1).max()
     assert np.abs(host(dG) - rdg).max() <= f32_tol(dtype) * max(np.abs(rdg).max(), sc * 1e-2), "dgamma"
     assert np.abs(host(dBt) - rdb).max() <= f32_tol(dtype) * max(np.abs(rdb).max(), sc * 1e-2), "dbeta"
@@ -595,3 +595,89 @@ def test_conv1x1_bn_maxpool_bwd_fused(hb, B, Nb, Ci, Co, L, act):
     check(host(dX), host(dX2), 2 * TOL[dtype], "fused vs unfused dX", ex_dx)    # both sides carry their own bf16 rounding
     check(host(dW), host(dW2), 2 * TOL[dtype], "fused vs unfused dW", ex_dw)
     assert torch.equal(dG, dG2) or np.abs(host(dG) - host(dG2)).max() <= 1e-5 * max(np.abs(rdg).max(), sc * 1e-2)
+
+
+@pytest.mark.parametrize("B,Nb,Ci,Co,L,act", [(2, 5, 16, 40, 300, 1), (2, 3, 128, 136, 260, 1), (3, 4, 64, 72, 132, 2),
+                                               (2, 3, 8, 1024, 8, 0), (1, 2, 128, 300, 1156, 1)])
+def test_conv1x1_bn_maxpool_fwd_bwd_one_operator(hb, B, Nb, Ci, Co, L, act):
+    """Forward and backward of the one-operator tail against the oracle's composition (which
+    rounds nothing inside the operator).  The argmax is decided on fp32 matrix products on the
+    GPU and in float64 by the oracle: indices must agree except at near-ties of the maximum,
+    and the backward is checked on the GPU's own indices."""
+    dtype = "bf16"
+    print(f"conv+bn+pool one operator B={B} Nb={Nb} Ci={Ci} Co={Co} L={L} act={act}", flush=True)
+    x = hi.snap(np.maximum(hi.normal(141, (Nb, B * Ci, L)) + 0.3, 0.0), dtype)
+    w = hi.normal(142, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    bias = hi.normal(143, (B * Co,), dtype, 0.1)
+    g = (hi.normal(144, (B * Co,)) * 0.3 + 1.0).astype(np.float32)
+    g[::3] = -np.abs(g[::3])                            # negative scales: the maximum sits at the minimum of z
+    bt = (hi.normal(145, (B * Co,)) * 0.3).astype(np.float32)
+    slope, eps, mom = 0.2, 1e-5, 0.1
+    oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
+    rm0 = (hi.normal(146, (B * Co,)) * 0.1).astype(np.float32)
+    rv0 = (1.0 + 0.1 * np.abs(hi.normal(147, (B * Co,)))).astype(np.float32)
+    rv, ri, rmean, rinv, nrm, nrv, rz = oa.conv1x1_bn_maxpool_fwd(B, x, w, bias, g, bt, eps, mom, rm0, rv0, oact, slope)
+    sx = conv_strides(B, Ci, L)
+    vs = (Nb * Co, Co, 1)
+    t3 = lambda a: np.ascontiguousarray(a.reshape(Nb, B, Co).transpose(1, 0, 2))
+    X, W, Bi = dev(x, dtype), dev(w, dtype), dev(bias, dtype)
+    G, Bt, RM, RV = dev(g), dev(bt), dev(rm0), dev(rv0)
+    SM, SI = empty((B * Co,), torch.float32), empty((B * Co,), torch.float32)
+    V = empty((B, Nb, Co), dtype)
+    I = torch.empty(B, Nb, Co, dtype=torch.int32, device="cuda")
+    ZH = empty((B, Nb, Co), torch.float32)
+    SAV = empty((hb.conv1x1_bn_maxpool_saved_floats(B, Ci, Co),), torch.float32)
+    nws = max(hb.conv1x1_bn_maxpool_fwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype]),
+              hb.conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype]))
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    hb.conv1x1_bn_maxpool_fwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bi, G, Bt, eps, mom, RM, RV, SM, SI, V, I, vs, ZH, SAV,
+                              act, slope, ws)
+    # statistics: fp32 Gram matrix; the variance loses relative accuracy E[z^2] / var
+    m = Nb * L
+    gm, gi_ = host(SM), host(SI)
+    z = oa.conv1x1_fwd(B, x, w, bias)
+    ez2 = (z ** 2).mean(axis=(0, 2))
+    var = 1.0 / rinv ** 2 - eps
+    assert np.all(np.abs(gm - rmean) <= 1e-5 * (np.abs(rmean) + np.sqrt(var) + np.sqrt(ez2))), "mean"
+    assert np.all(np.abs(gi_ - rinv) <= rinv * (1e-5 + 2e-6 * ez2 / (var + eps))), "invstd"
+    assert np.abs(host(RM) - nrm).max() <= 1e-5 * max(np.abs(nrm).max(), 1.0)
+    assert np.all(np.abs(host(RV) - nrv) <= 1e-5 * np.abs(nrv) + 2e-7 * ez2), "running_var"
+    # pooled value, argmax, z at the argmax
+    gv, gi, gz = host(V), host(I), host(ZH)
+    y = oa.bn_fwd(B, z, g, bt, eps)[0]
+    ya = oops.act_fwd(y, oact, slope)
+    check(gv, t3(oops.store(rv, dtype)), TOL[dtype], "pooled")
+    assert gi.min() >= 0 and gi.max() < L
+    at = np.take_along_axis(ya, gi.transpose(1, 0, 2).reshape(Nb, B * Co, 1).astype(np.int64), axis=2)[:, :, 0]
+    mism = gi != t3(ri)
+    scale = np.abs(ya).max()
+    assert np.all(t3(at)[mism] >= t3(rv)[mism] - 1e-5 * (np.abs(t3(rv)[mism]) + scale)), "argmax not at a near-tie"
+    assert mism.mean() <= 0.02, mism.mean()
+    zat = np.take_along_axis(z, gi.transpose(1, 0, 2).reshape(Nb, B * Co, 1).astype(np.int64), axis=2)[:, :, 0]
+    assert np.abs(gz - t3(zat)).max() <= 1e-5 * np.abs(z).max(), "z at the argmax"
+    # backward from the forward's own outputs, against the oracle's composition on the same indices
+    dv = hi.normal(148, (B, Nb, Co), dtype)
+    idx_o = gi.transpose(1, 0, 2).reshape(Nb, B * Co)
+    rdx, rdw, rdb, rdg, rdbt = oa.conv1x1_bn_maxpool_bwd(B, x, w, bias, g, bt, gm, gi_, dv.transpose(1, 0, 2).reshape(Nb, B * Co),
+                                                         idx_o, oact, slope)
+    dV = dev(dv, dtype)
+    dX = empty(x.shape, dtype)
+    dW = empty((B * Co, Ci), torch.float32)
+    dB0, dG, dBt = (empty((B * Co,), torch.float32) for _ in range(3))
+    hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bi, None, None, ZH, SAV, dV, I, vs, G, Bt, SM, SI, dX, sx,
+                              dW, dB0, dG, dBt, act, slope, ws)
+    sc = np.abs(dv).sum(axis=1).max()
+    assert np.abs(host(dG) - rdg).max() <= f32_tol(dtype) * max(np.abs(rdg).max(), sc * 1e-2), "dgamma"
+    assert np.abs(host(dBt) - rdbt).max() <= f32_tol(dtype) * max(np.abs(rdbt).max(), sc * 1e-2), "dbeta"
+    # a bias under a BatchNorm has no gradient (the oracle's is rounding of the fp32 statistics it was given)
+    assert float(dB0.abs().max()) == 0.0 and np.abs(rdb).max() <= 1e-5 * sc
+    e1 = check(host(dX), rdx, TOL[dtype], "dX")
+    e2 = check(host(dW), rdw, 2e-4, "dW")               # fp32 output, no storage rounding anywhere in the operator
+    print(f"   mismatching argmax {mism.mean():.2e}; rel err dX {e1:.2e} dW {e2:.2e}", flush=True)
+    # the same backward without the saved moments of the forward (recomputed from X)
+    dX2, dW2 = empty(x.shape, dtype), empty((B * Co, Ci), torch.float32)
+    hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bi, None, None, ZH, None, dV, I, vs, G, Bt, SM, SI, dX2,
+                              sx, dW2, dB0, dG, dBt, act, slope, ws)
+    check(host(dX2), rdx, TOL[dtype], "dX (moments recomputed)")
+    check(host(dW2), rdw, 2e-4, "dW (moments recomputed)")
