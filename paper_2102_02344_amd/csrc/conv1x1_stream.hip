@@ -1,5 +1,5 @@
-// Streaming forward kernel of the fused k=1 Conv1d for wide layers with few input channels
-// (fusion rules table, Conv1d row; the point-cloud models' 128 -> 1024 layer).
+// Streaming forward kernel of the fused k=1 Conv1d for layers with at most 128 input channels
+// (fusion rules table, Conv1d row; the point-cloud models' 64 -> 64 ... 128 -> 1024 layers).
 //
 // Per model b and sample n:  Y[co][l] = sum_ci W[b][co][ci] * X[ci][l] + bias[b][co], with Ci <= 128:
 // the whole reduction fits one LDS tile, so a generic k-loop kernel spends its time in launch,
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv1x1_stream_kernel(StreamArgs
 int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
                        const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st) {
   auto al = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; };
-  if (Ci > 128 || Ci % 8 != 0 || Co < 256 || L % 4 != 0) return HFTA_EUNSUPPORTED;
+  if (Ci > 128 || Ci % 8 != 0 || Co < 64 || L % 4 != 0) return HFTA_EUNSUPPORTED;
   if (act == HFTA_ACT_TANH || act == HFTA_ACT_GELU) return HFTA_EUNSUPPORTED;
   if (!al(W, 16) || !al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0) return HFTA_EUNSUPPORTED;
   const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2, w_ext = (int64_t)Co * Ci * 2;

@@ -525,11 +525,13 @@ struct FbpArgs {
   uint32_t x_extent, w_extent;
 };
 
-// One workgroup owns a 128-point slice of one sample: the X tile (transposed) stays in LDS, the
-// loop walks the 128-row tiles of W (next tile in flight in registers), and the epilogue of a
-// step is a per-lane scan of the accumulators for (max, first argmax) instead of a store.
+// One workgroup owns a 128-point slice of one sample; each wavefront keeps its half of the X tile
+// as matrix-instruction fragments in registers, the loop walks the 128-row tiles of W through two
+// LDS buffers (tile ct+1 parked, tile ct+2 in flight in registers while tile ct is multiplied: one
+// barrier per step), and the epilogue of a step is a per-lane scan of the accumulators for
+// (max, first argmax) instead of a store.
 template <int KT>
-__global__ __launch_bounds__(GEMM_THREADS) void fbp_main_kernel(FbpArgs p) {
+__global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) {   // two wavefronts per SIMD
   constexpr int PITCH = KT * 2 + 16;
   constexpr int TILE = 128 * PITCH;
   constexpr int SUB = KT / 32;
@@ -555,7 +557,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void fbp_main_kernel(FbpArgs p) {
   const int l0 = bx * 128;
   const __amdgpu_buffer_rsrc_t rw = pf_rsrc(p.W + (int64_t)b * p.Co * p.Ci, p.w_extent);
   const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + b * p.xsb + n * p.xsn, p.x_extent);
-  const float* gam = p.gamma + (int64_t)b * p.Co;
+  const __amdgpu_buffer_rsrc_t rgam = pf_rsrc(p.gamma + (int64_t)b * p.Co, (uint32_t)p.Co * 4u);
 
   {  // X tile, transposed in registers into [point][ci]
     const int kq = t % 8, ng = t / 8;
@@ -590,12 +592,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void fbp_main_kernel(FbpArgs p) {
   // negative gets the sign bit of every element flipped (exact), so that every channel looks for a maximum
   const int wr = t >> 2, wg = (t & 3) * 8;
   uint4 wq[SUB][2];
-  uint32_t flip[2];
+  uint32_t gq[2];                        // the rows' gamma, raw bits: looked at only when the tile is parked
   auto load_w = [&](int ct) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int row = ct * 128 + wr + 64 * h;
-      flip[h] = (row < p.Co && gam[row] < 0.f) ? 0x80008000u : 0u;
+      gq[h] = __builtin_amdgcn_raw_buffer_load_b32(rgam, (int)(row < p.Co ? (uint32_t)row * 4u : PF_OOB), 0, 0);
 #pragma unroll
       for (int s = 0; s < SUB; ++s) {
         const int k = s * 32 + wg;
@@ -621,30 +623,46 @@ __global__ __launch_bounds__(GEMM_THREADS) void fbp_main_kernel(FbpArgs p) {
       pidx[ct * 128 + t] = l0 + (hi ? pm_p[pb][1][t] : pm_p[pb][0][t]);
     }
   };
-
-  for (int ct = 0; ct < p.tiles_co; ++ct) {
+  auto park_w = [&](unsigned char* dst) {                // the W tile in registers -> LDS, sign-folded
 #pragma unroll
     for (int s = 0; s < SUB; ++s)
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const uint4 w = wq[s][h];
-        *reinterpret_cast<uint4*>(Ws + (wr + 64 * h) * PITCH + (s * 32 + wg) * 2) =
-            make_uint4(w.x ^ flip[h], w.y ^ flip[h], w.z ^ flip[h], w.w ^ flip[h]);
+        const uint32_t flip = __uint_as_float(gq[h]) < 0.f ? 0x80008000u : 0u;
+        *reinterpret_cast<uint4*>(dst + (wr + 64 * h) * PITCH + (s * 32 + wg) * 2) =
+            make_uint4(w.x ^ flip, w.y ^ flip, w.z ^ flip, w.w ^ flip);
       }
-    __syncthreads();
-    load_w(ct + 1);                      // past the last tile: rows >= Co, zeros, no traffic
-    if (ct == 0) {                       // this slice's part of sum_l x: thread (ci, half) adds 64 points in order
-      const int ci = t & 127, half = t >> 7;
-      if (ci < p.Ci) {
-        float sx = 0.f;
-        const unsigned char* col = Xs + (half * 64) * PITCH + ci * 2;
+  };
+
+  // The X operand of this wavefront never changes: its matrix-instruction fragments move from LDS
+  // into registers once, and the X tile's LDS becomes the second W buffer.
+  park_w(Ws);
+  __syncthreads();
+  load_w(1);
+  bf16x8_t xf[2][KT / 16];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int s = 0; s < KT / 16; ++s)
+      xf[j][s] = *reinterpret_cast<const bf16x8_t*>(Xs + (wn * 64 + j * 32 + r) * PITCH + (2 * s + gsel) * 16);
+  {  // this slice's part of sum_l x: thread (ci, half) adds 64 points in order
+    const int ci = t & 127, half = t >> 7;
+    if (ci < p.Ci) {
+      float sx = 0.f;
+      const unsigned char* col = Xs + (half * 64) * PITCH + ci * 2;
 #pragma unroll 8
-        for (int q = 0; q < 64; ++q) sx += bf16_to_f32(*reinterpret_cast<const bf16_raw*>(col + q * PITCH));
-        p.SXpart[(((int64_t)bz * tiles + bx) * 2 + half) * p.Ci + ci] = sx;
-      }
-    } else {
-      publish(ct - 1);
+      for (int q = 0; q < 64; ++q) sx += bf16_to_f32(*reinterpret_cast<const bf16_raw*>(col + q * PITCH));
+      p.SXpart[(((int64_t)bz * tiles + bx) * 2 + half) * p.Ci + ci] = sx;
     }
+  }
+  __syncthreads();                       // the X tile is dead
+
+  for (int ct = 0; ct < p.tiles_co; ++ct) {
+    unsigned char* cur = (ct & 1) ? Xs : Ws;
+    park_w((ct & 1) ? Ws : Xs);          // tile ct+1; that buffer was last read in step ct-1
+    load_w(ct + 2);                      // past the last tile: rows >= Co, zeros, no traffic
+    if (ct > 0) publish(ct - 1);
 
     f32x16_t acc[2][2];
 #pragma unroll
@@ -655,17 +673,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void fbp_main_kernel(FbpArgs p) {
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 #pragma unroll
     for (int s = 0; s < KT / 16; ++s) {
-      bf16x8_t a[2], bb[2];
+      bf16x8_t a[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[i] = *reinterpret_cast<const bf16x8_t*>(Ws + (wm * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
-        bb[i] = *reinterpret_cast<const bf16x8_t*>(Xs + (wn * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
-      }
+      for (int i = 0; i < 2; ++i)
+        a[i] = *reinterpret_cast<const bf16x8_t*>(cur + (wm * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j], a[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[j][s], a[i], acc[i][j], 0, 0, 0);
     }
     // lane = channel wm*64 + i*32 + (lane & 31); its 32 points wn*64 + j*32 + 8q + 4(lane>>5) + e in rising order
     float bv[2];
@@ -708,7 +724,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void fbp_main_kernel(FbpArgs p) {
         pm_p[ct & 1][wn][wm * 64 + i * 32 + lane] = bp[i];
       }
     }
-    __syncthreads();                     // every wavefront is done with the W tile; step ct's maxima are in LDS
+    __syncthreads();                     // tile ct+1 is in LDS, tile ct is free, step ct's maxima are published next
   }
   publish(p.tiles_co - 1);
 }
