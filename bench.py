@@ -87,7 +87,7 @@ def kernel_label(name, a):
         return f"{name}_{lay}_kernel"
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
-        if dt == 1 and Ci <= 128 and Ci % 8 == 0 and Co >= 256 and L % 4 == 0:
+        if dt == 1 and Ci <= 128 and Ci % 8 == 0 and Co >= 64 and L % 4 == 0:
             return "conv1x1_stream_kernel"
         return "gemm_pf_kernel(fwd)" if dt == 1 else "gemm_kernel(fwd)"
     if name == "linear_fwd":
