@@ -171,6 +171,106 @@ def pointnet_cls_inputs(spec: PointNetClsSpec, seed: Optional[int] = None) -> Di
 
 
 # --------------------------------------------------------------------------
+# PointNet-segmentation-style fused array (BASELINE config 2)
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class PointNetSegSpec:
+    """Per-point MLP, max over points, then a per-point head on the concatenation of every
+    per-point feature map, the tiled global feature and the tiled object-category one-hot."""
+    name: str
+    B: int
+    Nb: int
+    L: int
+    conv: Tuple[int, ...]     # per-point MLP channel chain, starts at 3
+    head: Tuple[int, ...]     # head channel chain; head[0] = sum(conv[1:]) + conv[-1] + n_cat, ends at n_parts
+    dtype: str
+    n_cat: int = 16
+    n_parts: int = 50
+    lr_range: Tuple[float, float] = (1e-4, 1e-2)
+    config_index: int = 2
+
+    @property
+    def c_point(self) -> int:          # channels of the concatenated per-point features
+        return sum(self.conv[1:])
+
+    @property
+    def c_global(self) -> int:         # tiled part: global feature + category one-hot
+        return self.conv[-1] + self.n_cat
+
+
+def spec_c2(B: int = 6, Nb: int = 16, L: int = 2500, dtype: str = "bf16") -> PointNetSegSpec:
+    conv = (3, 64, 128, 128, 512, 2048)
+    return PointNetSegSpec(name=f"c2_pointnet_seg_B{B}_{dtype}", B=B, Nb=Nb, L=L, conv=conv,
+                           head=(sum(conv[1:]) + conv[-1] + 16, 256, 256, 128, 50), dtype=dtype)
+
+
+def seg_thin(B: int, Nb: int, L: int, dtype: str, div: int = 8) -> PointNetSegSpec:
+    """Config 2's layer list with every hidden width divided by ``div`` (oracle-sized cases)."""
+    conv = (3,) + tuple(max(8, c // div) for c in (64, 128, 128, 512, 2048))
+    head_hidden = tuple(max(8, c // div) for c in (256, 256, 128))
+    return PointNetSegSpec(name=f"c2_thin{div}_B{B}_{dtype}", B=B, Nb=Nb, L=L, conv=conv,
+                           head=(sum(conv[1:]) + conv[-1] + 16,) + head_hidden + (50,), dtype=dtype)
+
+
+def pointnet_seg_param_shapes(spec: PointNetSegSpec) -> List[Tuple[str, Tuple[int, ...]]]:
+    """Per-model parameters in arena order.  The first head layer's ``[head[1], head[0]]`` weight is
+    kept as two blocks: ``head0.w`` ``[head[1], c_point]`` applied to the per-point features
+    (a k=1 convolution) and ``head0.wg`` ``[c_global, head[1]]`` applied once per sample to the tiled
+    part (a Linear); together they are the 4944-wide convolution of the layer list."""
+    out: List[Tuple[str, Tuple[int, ...]]] = []
+    for i in range(len(spec.conv) - 1):
+        ci, co = spec.conv[i], spec.conv[i + 1]
+        out += [(f"conv{i}.w", (co, ci)), (f"conv{i}.b", (co,)), (f"conv{i}.bn.g", (co,)), (f"conv{i}.bn.b", (co,))]
+    nh = len(spec.head) - 1
+    for i in range(nh):
+        ci, co = spec.head[i], spec.head[i + 1]
+        if i == 0:
+            out += [("head0.w", (co, spec.c_point)), ("head0.wg", (spec.c_global, co)), ("head0.b", (co,))]
+        else:
+            out += [(f"head{i}.w", (co, ci)), (f"head{i}.b", (co,))]
+        if i < nh - 1:
+            out += [(f"head{i}.bn.g", (co,)), (f"head{i}.bn.b", (co,))]
+    return out
+
+
+def pointnet_seg_inputs(spec: PointNetSegSpec, seed: Optional[int] = None) -> Dict[str, object]:
+    """points float32 [Nb, B*3, L]; labels int32 [B, Nb, L] (part of every point); category int32
+    [B, Nb] and its one-hot float32 [B, Nb, n_cat]; params; lr, beta1, beta2, eps, wd [B]."""
+    seed = config_seed(spec.config_index) if seed is None else seed
+    rngs = model_streams(seed, spec.B)
+    B, Nb, L = spec.B, spec.Nb, spec.L
+    points = np.empty((Nb, B * 3, L), dtype=np.float32)
+    labels = np.empty((B, Nb, L), dtype=np.int32)
+    cat = np.empty((B, Nb), dtype=np.int32)
+    params = []
+    lr = np.empty(B, np.float32)
+    shapes = pointnet_seg_param_shapes(spec)
+    for b, rng in enumerate(rngs):
+        points[:, 3 * b:3 * b + 3, :] = unit_ball_points(rng, Nb, L)
+        labels[b] = rng.integers(0, spec.n_parts, size=(Nb, L))
+        cat[b] = rng.integers(0, spec.n_cat, size=Nb)
+        p = {}
+        for name, shape in shapes:
+            layer = name.split(".")[0]
+            fan_in = spec.head[0] if layer == "head0" else dict(shapes)[layer + ".w"][1]
+            if name.endswith(".bn.g"):
+                p[name] = np.ones(shape, np.float32)
+            elif name.endswith(".bn.b"):
+                p[name] = np.zeros(shape, np.float32)
+            elif name.endswith(".w") or name.endswith(".wg"):
+                p[name] = uniform_fan_in(rng, shape, fan_in, 6.0).astype(np.float32)
+            else:
+                p[name] = uniform_fan_in(rng, shape, fan_in, 1.0).astype(np.float32)
+        params.append(p)
+        lr[b] = log_uniform(rng, *spec.lr_range)
+    onehot = np.zeros((B, Nb, spec.n_cat), np.float32)
+    np.put_along_axis(onehot, cat[:, :, None].astype(np.int64), 1.0, axis=2)
+    return dict(points=snap(points, spec.dtype), labels=labels, category=cat, onehot=onehot, params=params, lr=lr,
+                beta1=np.full(B, 0.9, np.float32), beta2=np.full(B, 0.999, np.float32),
+                eps=np.full(B, 1e-8, np.float32), wd=np.zeros(B, np.float32))
+
+
+# --------------------------------------------------------------------------
 # operator-level cases (shapes of the other workloads)
 # --------------------------------------------------------------------------
 def normal(seed: int, shape: Sequence[int], dtype: str = "f32", scale: float = 1.0) -> np.ndarray:

@@ -280,6 +280,38 @@ def maxpool_points_bwd(dv, idx, L: int):
 
 
 # --------------------------------------------------------------------------
+# Pieces of a segmentation head on a concatenation with a tiled (point-independent) part:
+# a k=1 convolution over [per-point features | tiled vector] equals the convolution over the
+# per-point features plus a per-sample vector broadcast along the points.
+# --------------------------------------------------------------------------
+def add_sample_bias(z, s):
+    """z:[N,C,L], s:[N,C] -> z + s broadcast along the points."""
+    return _f64(z) + _f64(s)[:, :, None]
+
+
+def sum_points(dz):
+    """Adjoint of the broadcast: dz:[N,C,L] -> [N,C], the sum over the points."""
+    return _f64(dz).sum(axis=2)
+
+
+def softmax_xent_points(logits, labels):
+    """logits:[N,K,L], labels:[N,L] int.  Softmax cross-entropy over the class axis K for every point,
+    mean over the N*L points.  Returns (loss, dlogits[N,K,L])."""
+    logits = _f64(logits)
+    N, K, L = logits.shape
+    loss, d = softmax_xent(logits.transpose(0, 2, 1).reshape(N * L, K), np.asarray(labels).reshape(-1))
+    return loss, d.reshape(N, L, K).transpose(0, 2, 1)
+
+
+def maxpool_points_bwd_add(dx, dv, idx):
+    """dx:[N,C,L] + (dv[n,c] at l = idx[n,c]): the max-pool's backward added onto another gradient."""
+    out = _f64(dx).copy()
+    N, C, _ = out.shape
+    out[np.arange(N)[:, None], np.arange(C)[None, :], np.asarray(idx, np.int64)] += _f64(dv)
+    return out
+
+
+# --------------------------------------------------------------------------
 # Tail of a point-cloud model's per-point MLP as ONE operator:
 #   k=1 Conv1d -> training-mode BatchNorm -> activation -> max over points
 # (rows "Conv1d", "BatchNorm1d" and the element-wise rows, then the point max-pool).  It is the

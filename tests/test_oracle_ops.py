@@ -424,3 +424,30 @@ def test_conv_bn_maxpool_operator(act):
     close(dg, fd_grad(lambda q: f(x, w, b, q, bt), g), 1e-5)
     close(dbt, fd_grad(lambda q: f(x, w, b, g, q), bt), 1e-5)
     assert np.abs(db).max() < 1e-12 and np.abs(fd_grad(lambda q: f(x, w, q, g, bt), b)).max() < 1e-6
+
+
+def test_segmentation_head_pieces():
+    """Brute-force loops; the broadcast/sum pair is an adjoint pair; the per-point loss against the
+    row form on an explicit transpose and by finite differences."""
+    N, C, L, K = 2, 3, 5, 4
+    z, s, dz = rnd(N, C, L), rnd(N, C), rnd(N, C, L)
+    y = ops.add_sample_bias(z, s)
+    for n in range(N):
+        for c in range(C):
+            for l in range(L):
+                assert y[n, c, l] == z[n, c, l] + s[n, c]
+    sp = ops.sum_points(dz)
+    assert abs((ops.add_sample_bias(np.zeros_like(z), s) * dz).sum() - (s * sp).sum()) < 1e-12     # <B s, dz> = <s, B^T dz>
+    logits, labels = rnd(N, K, L), RNG.integers(0, K, (N, L))
+    loss, d = ops.softmax_xent_points(logits, labels)
+    ref = 0.0
+    for n in range(N):
+        for l in range(L):
+            col = logits[n, :, l]
+            ref += math.log(sum(math.exp(q) for q in col)) - col[labels[n, l]]
+    assert abs(loss - ref / (N * L)) < 1e-12
+    close(d, fd_grad(lambda q: ops.softmax_xent_points(q, labels)[0], logits), 1e-6)
+    dx, dv = rnd(N, C, L), rnd(N, C)
+    idx = RNG.integers(0, L, (N, C))
+    out = ops.maxpool_points_bwd_add(dx, dv, idx)
+    close(out, dx + ops.maxpool_points_bwd(dv, idx, L), 1e-15)
