@@ -37,6 +37,7 @@ class Tracer:
                      "adam_step_multi", "linear_fwd", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
                      "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd",
                      "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_fwd",
+                     "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
                      "conv1x1_bn_maxpool_bwd")
 
     def __init__(self, hb, torch):
@@ -89,6 +90,8 @@ def kernel_label(name, a):
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci <= 128 and Ci % 8 == 0 and Co >= 64 and L % 4 == 0:
             return "conv1x1_stream_kernel"
+        if dt == 1 and big_gemm(B * Nb, Co, L, Ci):
+            return "gemm_big_kernel(fwd)"
         return "gemm_pf_kernel(fwd)" if dt == 1 else "gemm_kernel(fwd)"
     if name == "linear_fwd":
         if a[4] == 1 and big_gemm(a[0], a[1], a[3], a[2]):
@@ -103,6 +106,12 @@ def kernel_label(name, a):
         return "colsum_kernel"
     if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
+    if name in ("add_sample_bias", "add_strided"):
+        return "row_add_kernel"
+    if name == "sum_points":
+        return "sum_points_kernel"
+    if name == "softmax_xent_points":
+        return "xent_points_kernel"
     # the GAN array gives every convolution a workspace: column-buffer lowering, several kernels per call
     if name == "conv2d_grouped_fwd":
         return "conv2d fwd: im2col_lds_kernel + gemm"
@@ -110,8 +119,11 @@ def kernel_label(name, a):
         return ("conv2d dX: pack_dy_kernel + gemm + col2im_lds_kernel" if a[14] is not None
                 else "conv2d dW: pack_dy_kernel + im2col_lds_kernel + gemm")
     if name == "conv1x1_bwd":          # called with either dX or dW requested, never both
-        k = "gemm_pf_kernel" if a[5] == 1 else "gemm_kernel"
-        return k + ("(dX)" if a[11] is not None else "(dW)+splitk_reduce_kernel")
+        B, Nb, Ci, Co, L, dt = a[:6]
+        k = "gemm_pf_kernel" if dt == 1 else "gemm_kernel"
+        if a[11] is not None:
+            return ("gemm_big_kernel" if dt == 1 and big_gemm(B * Nb, Ci, L, Co) else k) + "(dX)"
+        return k + "(dW)+splitk_reduce_kernel"
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
     if name == "conv1x1_bn_maxpool_fwd":
@@ -197,6 +209,12 @@ def algorithmic_bytes(name, a):
         return act_bytes + wbytes * _es(dt)
     if name == "bias_act_nchw":
         return 2 * a[0] * a[1] * a[2] * _es(a[3])
+    if name in ("add_sample_bias", "softmax_xent_points"):
+        return 2 * a[0] * a[1] * a[2] * a[3] * _es(a[4])
+    if name == "add_strided":
+        return 3 * a[0] * a[1] * a[2] * a[3] * _es(a[4])
+    if name == "sum_points":
+        return a[0] * a[1] * a[2] * a[3] * _es(a[4])
     if name == "act_fwd":
         return 2 * a[0] * _es(a[1])
     if name in ("act_bwd", "add"):
@@ -314,6 +332,15 @@ class Workload:
             self.config = {"workload": self.spec.name, "B": self.spec.B, "batch_per_model": self.spec.Nb,
                            "points": self.spec.L, "conv": list(self.spec.conv), "fc": list(self.spec.fc),
                            "step": "fwd+bwd+Adam"}
+        elif name == "c2":
+            from oracle import pointnet_seg as oracle_model
+            self.spec = hi.spec_c2()
+            self.inp = hi.pointnet_seg_inputs(self.spec)
+            self.cls = arrays.FusedPointNetSeg
+            self.per_model_keys = ("labels", "onehot", "category")
+            self.config = {"workload": self.spec.name, "B": self.spec.B, "batch_per_model": self.spec.Nb,
+                           "points": self.spec.L, "conv": list(self.spec.conv), "head": list(self.spec.head),
+                           "step": "fwd+bwd+Adam"}
         elif name == "c3":
             from oracle import dcgan as oracle_model
             self.spec = hi.spec_c3()
@@ -340,8 +367,9 @@ class Workload:
         """(spec, inputs) of model b alone: the serial scheme's unit."""
         s1 = dataclasses.replace(self.spec, B=1)
         i1 = dict(self.inp)
-        if self.name in ("c0", "c1"):
+        if self.name in ("c0", "c1", "c2"):
             i1["points"] = np.ascontiguousarray(self.inp["points"][:, 3 * b:3 * b + 3])
+        if self.name in ("c0", "c1"):
             i1["drop_mask"] = None if self.inp["drop_mask"] is None else self.inp["drop_mask"][b:b + 1]
         for k in self.per_model_keys + ("lr", "beta1", "beta2", "eps", "wd"):
             i1[k] = self.inp[k][b:b + 1]
@@ -360,6 +388,11 @@ class Workload:
         if self.name in ("c0", "c1"):
             small = dataclasses.replace(self.spec, B=1, Nb=min(16, self.spec.Nb))
             inp = hi.pointnet_cls_inputs(small)
+            nsamp = small.Nb
+            what = f"1 model x {small.Nb} clouds x {small.L} points"
+        elif self.name == "c2":
+            small = dataclasses.replace(self.spec, B=1, Nb=2)
+            inp = hi.pointnet_seg_inputs(small)
             nsamp = small.Nb
             what = f"1 model x {small.Nb} clouds x {small.L} points"
         elif self.name == "c3":
@@ -397,7 +430,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c3", "c4"])
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--ops-report", default=None,

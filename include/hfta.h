@@ -318,6 +318,37 @@ int hfta_act_bwd(int64_t count, int dtype, const void* Z, const void* dY, void* 
  * the MLP-block workload; fusion rules table, element-wise operators keep their shape with the
  * model dimension folded in).  Y may alias A or B.  Device pointers; EINVAL on null / count <= 0. */
 int hfta_add(int64_t count, int dtype, const void* A, const void* B, void* Y, void* stream);
+/* ------------------------------------------------------------------------
+ * Pieces of a per-point (segmentation) head whose input is a concatenation of feature maps with a
+ * tiled, point-independent part (the point-cloud segmentation workload of section "Methodology";
+ * concatenation and tiling are element-wise in the model index, so they are expressed by strides:
+ * a feature map is a channel slice of one [Nb][B*Ctot][L] buffer, nothing is copied).
+ * Tensors are [b][n][c][l] with explicit element strides s[4] (unit point stride required) or
+ * [b][n][c] with strides s[3]; storage dtype; device pointers; EINVAL on null / non-positive sizes.
+ *   add_sample_bias: Y[b,n,c,l] = Z[b,n,c,l] + S[b,n,c]   (a k=1 convolution over [features | tiled
+ *                    vector] = convolution over the features + the tiled part's product, once per sample)
+ *   sum_points:      S[b,n,c] = sum_l X[b,n,c,l]           (its adjoint; fp32 accumulation, fixed order)
+ *   add_strided:     Y = A + B element-wise                (gradient of a slice + gradient from the next layer)
+ *   maxpool_points_bwd_add: dX[b,n,c,idx[b,n,c]] += dV[b,n,c] in place (hfta_maxpool_points_bwd added
+ *                    onto an existing gradient; idx clamped to [0, L); dV, idx with strides vs)
+ *   softmax_xent_points: scores [b][n][k][l], labels int32 [B][Nb][L]; per point softmax cross-entropy
+ *                    over k; loss[b] (fp32) = mean over the model's Nb*L points; dlogits = its gradient.
+ *                    Workspace: hfta_softmax_xent_points_workspace_bytes (EWORKSPACE below it).
+ * Y may alias A (and Z).
+ * ---------------------------------------------------------------------- */
+int hfta_add_sample_bias(int B, int Nb, int C, int L, int dtype, const void* Z, const int64_t zs[4],
+                         const void* S, const int64_t ss[3], void* Y, const int64_t ys[4], void* stream);
+int hfta_sum_points(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4],
+                    void* S, const int64_t ss[3], void* stream);
+int hfta_add_strided(int B, int Nb, int C, int L, int dtype, const void* A, const int64_t as[4],
+                     const void* Bt, const int64_t bs[4], void* Y, const int64_t ys[4], void* stream);
+int hfta_maxpool_points_bwd_add(int B, int Nb, int C, int L, int dtype, const void* dV, const int32_t* idx,
+                                const int64_t vs[3], void* dX, const int64_t dxs[4], void* stream);
+size_t hfta_softmax_xent_points_workspace_bytes(int B, int Nb, int L);
+int hfta_softmax_xent_points(int B, int Nb, int K, int L, int dtype, const void* logits, const int64_t ls[4],
+                             const int32_t* labels, float* loss, void* dlogits, const int64_t ds[4],
+                             void* workspace, size_t ws_bytes, void* stream);
+
 /* Adds a per-channel bias to an [Nb][K][HW] tensor (K = B*C channels) and applies act, in place. */
 int hfta_bias_act_nchw(int64_t Nb, int64_t K, int64_t HW, int dtype, void* Y, const void* bias,
                        int act, float slope, void* stream);

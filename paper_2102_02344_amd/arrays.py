@@ -672,3 +672,184 @@ class FusedDcgan:
         self.g_step_backward()
         self.G.adam()
         return self.loss_g
+
+
+class FusedPointNetSeg(ParamArena):
+    """PointNet-segmentation-style array: per-point k=1 convolutions + BatchNorm + ReLU, max over the
+    points of the last feature map, then a per-point head on the concatenation of every feature map,
+    the tiled global feature and the tiled category one-hot; softmax cross-entropy per point; Adam.
+
+    Nothing is copied to concatenate: every per-point layer writes its activation into its channel
+    slice of one ``[Nb, B*c_point, L]`` buffer (strides), the head's first convolution reads that
+    buffer as one 2880-channel input, and the tiled part enters as ``[global | one-hot] @ Wg`` once per
+    sample, broadcast along the points.  Backward mirrors it: the head's data gradient lands in a
+    buffer of the same shape, and each per-point layer adds its slice to the gradient from the
+    next layer."""
+
+    BN_EPS = 1e-5
+    BN_MOMENTUM = 0.1
+
+    def __init__(self, spec, inp: dict, device: str = "cuda"):
+        self.spec = spec
+        self.B, self.Nb, self.L = spec.B, spec.Nb, spec.L
+        self.dtype, self.dt, self.tdt = spec.dtype, _DT[spec.dtype], _TDT[spec.dtype]
+        self.dev = torch.device(device)
+        B, Nb, L = self.B, self.Nb, self.L
+        import hfta_inputs as hi
+        self._init_arena(hi.pointnet_seg_param_shapes(spec), B, inp, spec.dtype, self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        act = dict(dtype=self.tdt, device=self.dev)
+        self.running: Dict[str, torch.Tensor] = {}
+        self.saved: Dict[str, torch.Tensor] = {}
+        for name, shp in self.shapes:
+            if name.endswith(".bn.g"):
+                k = name[:-2]
+                self.running[k + ".rm"] = torch.zeros(B * shp[0], **f32)
+                self.running[k + ".rv"] = torch.ones(B * shp[0], **f32)
+                self.saved[k + ".mean"] = torch.empty(B * shp[0], **f32)
+                self.saved[k + ".invstd"] = torch.empty(B * shp[0], **f32)
+        self.nconv, self.nh = len(spec.conv) - 1, len(spec.head) - 1
+        self.Cp, self.Cg, self.C4 = spec.c_point, spec.c_global, spec.conv[-1]
+        self.off = [0]
+        for c in spec.conv[1:]:
+            self.off.append(self.off[-1] + c)
+        Cp, Cg = self.Cp, self.Cg
+        self.cat = torch.empty(Nb, B * Cp, L, **act)
+        self.dcat = torch.empty(Nb, B * Cp, L, **act)
+        self.cat_strides = (Cp * L, B * Cp * L, L, 1)
+        self.z = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:]]
+        self.gfeat = torch.zeros(B, Nb, Cg, **act)
+        self.gfeat[:, :, self.C4:] = torch.from_numpy(inp["onehot"]).to(self.tdt).to(self.dev)
+        self.pool_idx = torch.zeros(B, Nb, Cg, dtype=torch.int32, device=self.dev)
+        self.gvs = (Nb * Cg, Cg, 1)
+        H = spec.head
+        self.hg = torch.empty(B, Nb, H[1], **act)
+        self.dhg = torch.empty(B, Nb, H[1], **act)
+        self.dgfeat = torch.empty(B, Nb, Cg, **act)
+        self.zh = [torch.empty(Nb, B * c, L, **act) for c in H[1:]]
+        self.ah = [torch.empty(Nb, B * c, L, **act) for c in H[1:-1]]
+        cmax = max(max(spec.conv[1:]), max(H[1:]))
+        self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(3)]
+        self.loss = torch.empty(B, **f32)
+        ws = max(4, hb.softmax_xent_points_workspace_bytes(B, Nb, L), hb.linear_bwd_workspace_bytes(B, Nb, Cg, H[1], self.dt))
+        for i in range(self.nconv):
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
+        for i in range(self.nh):
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, Cp if i == 0 else H[i], H[i + 1], L, self.dt))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+        self.points = torch.from_numpy(inp["points"]).to(self.tdt).to(self.dev)
+        self.labels = torch.from_numpy(inp["labels"]).to(self.dev)
+
+    def _slice(self, buf, i):
+        """Channel slice i of a concatenation buffer: (tensor whose data pointer is the slice's first
+        element, for the ABI; the same slice as a [Nb, B, C, L] view, for tests)."""
+        o, c = self.off[i], self.spec.conv[i + 1]
+        return buf.view(-1)[o * self.L:], buf.view(self.Nb, self.B, self.Cp, self.L)[:, :, o:o + c, :]
+
+    def forward_backward(self, probe=None):
+        s, B, Nb, L, dt = self.spec, self.B, self.Nb, self.L, self.dt
+        eps, mom = self.BN_EPS, self.BN_MOMENTUM
+        P = probe if probe is not None else (lambda op, **kw: None)
+        cst, Cp, Cg, C4, H = self.cat_strides, self.Cp, self.Cg, self.C4, s.head
+        bn = lambda k: (self.master(k + ".bn.g"), self.master(k + ".bn.b"))
+        st = lambda k: (self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"])
+        # ---- per-point MLP: each activation goes straight into its slice of the concatenation
+        x, xs, xv, ci = self.points, _cs(B, 3, L), self.points, 3
+        for i in range(self.nconv):
+            co, k = s.conv[i + 1], f"conv{i}"
+            hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, xs, self.w(k + ".w"), self.w(k + ".b"), self.z[i], _cs(B, co, L))
+            P("conv1x1_fwd", layer=k, x=xv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
+            a, av = self._slice(self.cat, i)
+            hb.bn_fwd(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *bn(k), eps, mom, self.running[k + ".bn.rm"],
+                      self.running[k + ".bn.rv"], *st(k), a, cst, hb.ACT_RELU)
+            P("bn_fwd", layer=k, x=self.z[i], g=bn(k)[0], b=bn(k)[1], y=av, mean=st(k)[0], invstd=st(k)[1])
+            x, xs, xv, ci = a, cst, av, co
+        hb.maxpool_points(B, Nb, C4, L, dt, x, cst, self.gfeat, self.pool_idx, self.gvs)
+        P("maxpool_points", x=xv, v=self.gfeat[:, :, :C4], idx=self.pool_idx[:, :, :C4])
+        # ---- head: first layer = per-point block over the concatenation + once-per-sample block
+        hb.linear_fwd(B, Nb, Cg, H[1], dt, self.gfeat, self.w("head0.wg"), None, self.hg)
+        P("linear_fwd", layer="head0.wg", x=self.gfeat, w=self.w("head0.wg"), y=self.hg)
+        h, hs, hv, ci = self.cat, cst, self.cat, Cp
+        for i in range(self.nh):
+            co, k = H[i + 1], f"head{i}"
+            cs = _cs(B, co, L)
+            hb.conv1x1_fwd(B, Nb, ci, co, L, dt, h, hs, self.w(k + ".w"), self.w(k + ".b"), self.zh[i], cs)
+            P("conv1x1_fwd", layer=k, x=hv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.zh[i])
+            if i == 0:
+                zin = self.zh[0].clone() if probe is not None else None
+                hb.add_sample_bias(B, Nb, co, L, dt, self.zh[0], cs, self.hg, (Nb * co, co, 1), self.zh[0], cs)
+                P("add_sample_bias", z=zin, s=self.hg, y=self.zh[0])
+            if i == self.nh - 1:
+                break
+            hb.bn_fwd(B, Nb, co, L, dt, self.zh[i], cs, *bn(k), eps, mom, self.running[k + ".bn.rm"],
+                      self.running[k + ".bn.rv"], *st(k), self.ah[i], cs, hb.ACT_RELU)
+            P("bn_fwd", layer=k, x=self.zh[i], g=bn(k)[0], b=bn(k)[1], y=self.ah[i], mean=st(k)[0], invstd=st(k)[1])
+            h, hs, hv, ci = self.ah[i], cs, self.ah[i], co
+        K = H[-1]
+        logits = self.zh[-1]
+        d = self.dbuf[0][:Nb * B * K * L]
+        hb.softmax_xent_points(B, Nb, K, L, dt, logits, _cs(B, K, L), self.labels, self.loss, d, _cs(B, K, L), self.ws)
+        P("softmax_xent_points", logits=logits, labels=self.labels, loss=self.loss, d=d.view(Nb, B * K, L))
+
+        # ---- backward: head
+        cur = 0
+        for i in reversed(range(self.nh)):
+            ci, co, k = (Cp if i == 0 else H[i]), H[i + 1], f"head{i}"
+            cs = _cs(B, co, L)
+            if i < self.nh - 1:
+                dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
+                hb.bn_bwd(B, Nb, co, L, dt, self.zh[i], cs, d, cs, *bn(k), *st(k), dz, cs, self.g(k + ".bn.g"),
+                          self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.g(k + ".b"))
+                P("bn_bwd", layer=k, x=self.zh[i], dy=d.view(Nb, B * co, L), g=bn(k)[0], b=bn(k)[1], mean=st(k)[0],
+                  invstd=st(k)[1], dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"), db=self.g(k + ".bn.b"))
+                d, cur = dz, cur ^ 1
+            hin, hs = (self.cat, cst) if i == 0 else (self.ah[i - 1], _cs(B, ci, L))
+            dx, dxs = (self.dcat, cst) if i == 0 else (self.dbuf[cur ^ 1][:Nb * B * ci * L], _cs(B, ci, L))
+            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, self.w(k + ".w"), d, cs, dx, dxs, None, None, None)
+            own_db = self.g(k + ".b") if i == self.nh - 1 else None      # else from the BatchNorm backward
+            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, hin, hs, None, d, cs, None, None, self.g(k + ".w"), own_db, self.ws)
+            P("conv1x1_bwd", layer=k, x=hin, w=self.w(k + ".w"), dy=d.view(Nb, B * co, L),
+              dx=dx.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"))
+            if i == 0:
+                hb.sum_points(B, Nb, co, L, dt, d, cs, self.dhg, (Nb * co, co, 1))
+                P("sum_points", x=d.view(Nb, B * co, L), s=self.dhg)
+                hb.linear_bwd(B, Nb, Cg, co, dt, self.gfeat, self.w("head0.wg"), self.dhg, self.dgfeat,
+                              self.g("head0.wg"), None, self.ws)
+                P("linear_bwd", layer="head0.wg", x=self.gfeat, w=self.w("head0.wg"), dy=self.dhg, dx=self.dgfeat,
+                  dw=self.g("head0.wg"))
+            else:
+                d, cur = dx, cur ^ 1
+
+        # ---- backward: per-point MLP; each layer adds its slice of the concatenation's gradient
+        dnext = None
+        for i in reversed(range(self.nconv)):
+            ci, co, k = s.conv[i], s.conv[i + 1], f"conv{i}"
+            cs = _cs(B, co, L)
+            sl, slv = self._slice(self.dcat, i)
+            if i == self.nconv - 1:
+                before = slv.clone() if probe is not None else None
+                hb.maxpool_points_bwd_add(B, Nb, co, L, dt, self.dgfeat, self.pool_idx, self.gvs, sl, cst)
+                P("maxpool_points_bwd_add", dx0=before, dv=self.dgfeat[:, :, :C4], idx=self.pool_idx[:, :, :C4], dx=slv)
+                da, das, dav = sl, cst, slv
+            else:
+                dsum = self.dbuf[2][:Nb * B * co * L]
+                hb.add_strided(B, Nb, co, L, dt, dnext, cs, sl, cst, dsum, cs)
+                P("add_strided", a=dnext.view(Nb, B * co, L), b=slv, y=dsum.view(Nb, B * co, L))
+                da, das, dav = dsum, cs, dsum.view(Nb, B * co, L)
+            dz = self.dbuf[0][:Nb * B * co * L]
+            hb.bn_bwd(B, Nb, co, L, dt, self.z[i], cs, da, das, *bn(k), *st(k), dz, cs, self.g(k + ".bn.g"),
+                      self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.g(k + ".b"))
+            P("bn_bwd", layer=k, x=self.z[i], dy=dav, g=bn(k)[0], b=bn(k)[1], mean=st(k)[0], invstd=st(k)[1],
+              dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"), db=self.g(k + ".bn.b"))
+            if i > 0:
+                xin, xs = self._slice(self.cat, i - 1)[0], cst
+                xinv = self._slice(self.cat, i - 1)[1]
+                dnext = self.dbuf[1][:Nb * B * ci * L]
+                hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, self.w(k + ".w"), dz, cs, dnext, _cs(B, ci, L),
+                               None, None, None)
+            else:
+                xin, xs, xinv, dnext = self.points, _cs(B, 3, L), self.points, None
+            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, xs, None, dz, cs, None, None, self.g(k + ".w"), None, self.ws)
+            P("conv1x1_bwd", layer=k, x=xinv, w=self.w(k + ".w"), dy=dz.view(Nb, B * co, L),
+              dx=None if i == 0 else dnext.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"))
+        return self.loss

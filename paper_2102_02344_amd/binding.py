@@ -58,6 +58,12 @@ _SIGS = {
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
     "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 21 + [_i, _f, _p, _sz, _p]),
+    "hfta_add_sample_bias": (_i, [_i] * 5 + [_p] * 7),
+    "hfta_sum_points": (_i, [_i] * 5 + [_p] * 5),
+    "hfta_add_strided": (_i, [_i] * 5 + [_p] * 7),
+    "hfta_maxpool_points_bwd_add": (_i, [_i] * 5 + [_p] * 6),
+    "hfta_softmax_xent_points_workspace_bytes": (_sz, [_i] * 3),
+    "hfta_softmax_xent_points": (_i, [_i] * 5 + [_p] * 7 + [_sz, _p]),
     "hfta_conv1x1_bn_maxpool_saved_floats": (_sz, [_i] * 3),
     "hfta_conv1x1_bn_maxpool_fwd_workspace_bytes": (_sz, [_i] * 6),
     "hfta_conv1x1_bn_maxpool_fwd": (_i, [_i] * 6 + [_p] * 6 + [_f, _f] + [_p] * 9 + [_i, _f, _p, _sz, _p]),
@@ -339,3 +345,33 @@ def mse(B, R, dtype, pred, target, loss, dpred, stream=None):
 def raw():
     """The ctypes library handle (for status-code tests that must not raise)."""
     return _lib
+
+
+def add_sample_bias(B, Nb, C, L, dtype, Z, zs, S, ss, Y, ys, stream=None):
+    _check(_lib.hfta_add_sample_bias(B, Nb, C, L, dtype, _ptr(Z), _strides(zs), _ptr(S), _strides(ss, 3), _ptr(Y),
+                                     _strides(ys), _stream(stream)), "hfta_add_sample_bias")
+
+
+def sum_points(B, Nb, C, L, dtype, X, xs, S, ss, stream=None):
+    _check(_lib.hfta_sum_points(B, Nb, C, L, dtype, _ptr(X), _strides(xs), _ptr(S), _strides(ss, 3), _stream(stream)),
+           "hfta_sum_points")
+
+
+def add_strided(B, Nb, C, L, dtype, A, as_, Bt, bs, Y, ys, stream=None):
+    _check(_lib.hfta_add_strided(B, Nb, C, L, dtype, _ptr(A), _strides(as_), _ptr(Bt), _strides(bs), _ptr(Y),
+                                 _strides(ys), _stream(stream)), "hfta_add_strided")
+
+
+def maxpool_points_bwd_add(B, Nb, C, L, dtype, dV, idx, vs, dX, dxs, stream=None):
+    _check(_lib.hfta_maxpool_points_bwd_add(B, Nb, C, L, dtype, _ptr(dV), _ptr(idx), _strides(vs, 3), _ptr(dX),
+                                            _strides(dxs), _stream(stream)), "hfta_maxpool_points_bwd_add")
+
+
+def softmax_xent_points_workspace_bytes(B, Nb, L):
+    return _lib.hfta_softmax_xent_points_workspace_bytes(B, Nb, L)
+
+
+def softmax_xent_points(B, Nb, K, L, dtype, logits, ls, labels, loss, dlogits, ds, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_softmax_xent_points(B, Nb, K, L, dtype, _ptr(logits), _strides(ls), _ptr(labels), _ptr(loss),
+                                         _ptr(dlogits), _strides(ds), wp, wb, _stream(stream)), "hfta_softmax_xent_points")

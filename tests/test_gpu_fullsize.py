@@ -299,3 +299,101 @@ def test_c3_conv2d_full_size_sampled(Ci, Co, H):
                 acc += (dYh[n[q], b[q] * Co:(b[q] + 1) * Co, ty // s, tx // s] * Wh[b[q] * Co:(b[q] + 1) * Co, c[q], ky_, kx_]).sum()
         ref[q] = acc
     rel_ok(got, ref, TOL["bf16"], "dX")
+
+
+def test_c2_full_size_step_sampled():
+    """Config 2 as benchmarked: B=6, bf16, 16 clouds x 2500 points per model, 2880-channel
+    concatenation.  The calls that are new at this size (convolutions over channel slices of the
+    concatenation buffers, K = 2880 and 512 -> 2048 GEMMs, the head's strided support operators)
+    are checked on seeded samples recomputed from the bits the GPU read."""
+    from paper_2102_02344_amd.arrays import FusedPointNetSeg
+    spec = hi.spec_c2()
+    inp = hi.pointnet_seg_inputs(spec)
+    arr = FusedPointNetSeg(spec, inp)
+    B, Nb, L = spec.B, spec.Nb, spec.L
+    rng = np.random.default_rng(21)
+    tol = TOL["bf16"]
+    seen = []
+    S = 1500
+
+    def v4(t, C):                      # [Nb, B*C, L] or [Nb, B, C, L] -> [Nb, B, C, L] view
+        return t if t.dim() == 4 else t.view(Nb, B, C, L)
+
+    def pick(*dims):
+        return [torch.from_numpy(rng.integers(0, m, S)).cuda() for m in dims]
+
+    def probe(op, **kw):
+        lay = kw.get("layer", "")
+        if op == "conv1x1_fwd" and lay in ("conv4", "head0", "head3"):
+            print("full-size check", op, lay, flush=True)
+            Co = kw["y"].shape[1] // B
+            w = kw["w"].view(B, Co, -1)
+            Ci = w.shape[2]
+            x, y = v4(kw["x"], Ci), v4(kw["y"], Co)
+            n, b, o, l = pick(Nb, B, Co, L)
+            ref = (f64(x[n, b, :, l]) * f64(w[b, o])).sum(axis=1) + f64(kw["b"].view(B, Co)[b, o])
+            rel_ok(f64(y[n, b, o, l]), ref, tol, f"{lay} fwd")
+            seen.append(op + lay)
+        elif op == "add_sample_bias":
+            C = kw["s"].shape[2]
+            n, b, c, l = pick(Nb, B, C, L)
+            ref = f64(v4(kw["z"], C)[n, b, c, l]) + f64(kw["s"][b, n, c])
+            rel_ok(f64(v4(kw["y"], C)[n, b, c, l]), oops.store(ref, "bf16"), 1e-6, op)
+            seen.append(op)
+        elif op == "softmax_xent_points":
+            K = kw["logits"].shape[1] // B
+            lg, d = v4(kw["logits"], K), v4(kw["d"], K)
+            n, b, l = pick(Nb, B, L)
+            z = f64(lg[n, b, :, l])                                                         # [S, K]
+            lab = kw["labels"][b, n, l].cpu().numpy()
+            lse = np.log(np.exp(z - z.max(axis=1, keepdims=True)).sum(axis=1)) + z.max(axis=1)
+            p = np.exp(z - lse[:, None])
+            p[np.arange(S), lab] -= 1.0
+            rel_ok(f64(d[n, b, :, l]), p / (Nb * L), tol, "dlogits")
+            for bb in range(B):                                                             # the loss in full, per model
+                zb = f64(lg[:, bb]).transpose(0, 2, 1).reshape(Nb * L, K)
+                rl, _ = oops.softmax_xent(zb, kw["labels"][bb].cpu().numpy().reshape(-1))
+                assert abs(float(kw["loss"][bb]) - rl) <= 1e-5 * abs(rl)
+            seen.append(op)
+        elif op == "sum_points":
+            C = kw["s"].shape[2]
+            for b, n, c in zip(*(rng.integers(0, m, 16) for m in (B, Nb, C))):
+                ref = f64(v4(kw["x"], C)[n, b, c]).sum()
+                assert abs(float(kw["s"][b, n, c]) - ref) <= tol * max(abs(ref), 1e-2 * np.abs(f64(v4(kw["x"], C)[n, b, c])).sum())
+            seen.append(op)
+        elif op == "add_strided":
+            C = kw["y"].shape[1] // B
+            n, b, c, l = pick(Nb, B, C, L)
+            ref = f64(v4(kw["a"], C)[n, b, c, l]) + f64(v4(kw["b"], C)[n, b, c, l])
+            rel_ok(f64(v4(kw["y"], C)[n, b, c, l]), oops.store(ref, "bf16"), 1e-6, op)
+            seen.append(op)
+        elif op == "maxpool_points_bwd_add":
+            C = kw["dv"].shape[2]
+            idx = kw["idx"].long()
+            got = torch.gather(kw["dx"], 3, idx.permute(1, 0, 2).unsqueeze(3))[..., 0]       # [Nb, B, C] at the argmax
+            was = torch.gather(kw["dx0"], 3, idx.permute(1, 0, 2).unsqueeze(3))[..., 0]
+            ref = oops.store(f64(was) + f64(kw["dv"]).transpose(1, 0, 2), "bf16")
+            assert np.abs(f64(got) - ref).max() <= 1e-6 * max(np.abs(ref).max(), 1e-30)
+            # everything else is untouched: the number of changed elements is at most one per (n, b, c)
+            assert int((kw["dx"] != kw["dx0"]).sum()) <= Nb * B * C
+            seen.append(op)
+        elif op == "conv1x1_bwd" and lay in ("head0", "conv4"):
+            print("full-size check", op, lay, flush=True)
+            Co = kw["dy"].shape[1] // B
+            w = kw["w"].view(B, Co, -1)
+            Ci = w.shape[2]
+            x, dy, dx = v4(kw["x"], Ci), v4(kw["dy"], Co), v4(kw["dx"], Ci)
+            n, b, c, l = pick(Nb, B, Ci, L)
+            rel_ok(f64(dx[n, b, c, l]), (f64(dy[n, b, :, l]) * f64(w[b, :, c])).sum(axis=1), tol, f"{lay} dX")
+            dw = kw["dw"].view(B, Co, Ci)
+            for b_, o, c_ in zip(*(rng.integers(0, m, 16) for m in (B, Co, Ci))):
+                d_, x_ = f64(dy[:, b_, o]), f64(x[:, b_, c_])
+                ref, terms = (d_ * x_).sum(), np.abs(d_ * x_).sum()
+                assert abs(float(dw[b_, o, c_]) - ref) <= 2e-4 * max(abs(ref), 1e-2 * terms), f"{lay} dW"
+            seen.append(op + lay)
+
+    arr.forward_backward(probe)
+    torch.cuda.synchronize()
+    assert set(seen) == {"conv1x1_fwdconv4", "conv1x1_fwdhead0", "conv1x1_fwdhead3", "add_sample_bias", "softmax_xent_points",
+                         "sum_points", "add_strided", "maxpool_points_bwd_add", "conv1x1_bwdhead0", "conv1x1_bwdconv4"}
+    assert np.all(np.isfinite(arr.loss.cpu().numpy()))

@@ -1,0 +1,193 @@
+"""The PointNet-segmentation-style array (BASELINE config 2's layer list) and its support operators
+on the GPU against the oracle: the five strided operators on their own, every library call of a
+step in place on the bits the GPU consumed, and the free-running step (loss, gradients, Adam)
+against B separate unfused oracle runs."""
+import numpy as np
+import pytest
+import torch
+
+import hfta_inputs as hi
+from oracle import ops as oops
+from oracle import pointnet_seg as oseg
+from test_gpu_pointnet import CHAIN_TOL, in_place_probe
+from util import DT, TOL, check
+
+pytestmark = pytest.mark.gpu
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def H(t):
+    return t.cpu().numpy() if t.dtype in (torch.int32, torch.uint8) else t.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2102_02344_amd import binding
+    return binding
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,C,L,Ctot,off", [(2, 3, 5, 300, 12, 4), (3, 2, 8, 131, 8, 0)])
+def test_strided_support_ops(hb, dtype, B, Nb, C, L, Ctot, off):
+    """Operands are channel slices [off, off+C) of [Nb, B*Ctot, L] buffers, as the array uses them
+    (L = 131: no vector path; off = 0, Ctot = C: the dense case)."""
+    print(f"support ops {dtype} B={B} Nb={Nb} C={C} L={L} Ctot={Ctot} off={off}", flush=True)
+    tdt = TDT[dtype]
+    big = lambda seed: torch.from_numpy(hi.normal(seed, (Nb, B * Ctot, L), dtype)).to(tdt).cuda()
+    sl = lambda t: (t.view(-1)[off * L:], t.view(Nb, B, Ctot, L)[:, :, off:off + C, :])
+    sst = (Ctot * L, B * Ctot * L, L, 1)
+    dst = (C * L, B * C * L, L, 1)
+    per = lambda v: H(v).reshape(Nb, B * C, L)                       # [Nb,B,C,L] view -> [Nb, B*C, L]
+    t3 = lambda a: np.ascontiguousarray(np.asarray(a).reshape(Nb, B, C).transpose(1, 0, 2))   # [Nb, B*C] -> [B, Nb, C]
+    # add_sample_bias (in place on a slice) and sum_points
+    Z = big(1)
+    zp, zv = sl(Z)
+    z0 = per(zv)
+    S = torch.from_numpy(hi.normal(2, (B, Nb, C), dtype)).to(tdt).cuda()
+    s_nc = H(S).transpose(1, 0, 2).reshape(Nb, B * C)
+    hb.add_sample_bias(B, Nb, C, L, DT[dtype], zp, sst, S, (Nb * C, C, 1), zp, sst)
+    check(per(zv), oops.add_sample_bias(z0, s_nc), TOL[dtype], "add_sample_bias")
+    if off > 0:                                                       # the neighbouring channels are untouched
+        assert torch.equal(Z.view(Nb, B, Ctot, L)[:, :, :off], big(1).view(Nb, B, Ctot, L)[:, :, :off])
+    SP = torch.empty(B, Nb, C, dtype=tdt, device="cuda")
+    hb.sum_points(B, Nb, C, L, DT[dtype], zp, sst, SP, (Nb * C, C, 1))
+    check(H(SP), t3(oops.sum_points(per(zv))), TOL[dtype], "sum_points")
+    # add_strided: dense + slice -> dense
+    A = torch.from_numpy(hi.normal(3, (Nb, B * C, L), dtype)).to(tdt).cuda()
+    Y = torch.empty_like(A)
+    hb.add_strided(B, Nb, C, L, DT[dtype], A, dst, zp, sst, Y, dst)
+    check(H(Y), H(A) + per(zv), TOL[dtype], "add_strided")
+    # maxpool_points_bwd_add on the slice, dV / idx as the first C columns of wider [B, Nb, C+3] tensors
+    dV = torch.from_numpy(hi.normal(4, (B, Nb, C + 3), dtype)).to(tdt).cuda()
+    idx = torch.from_numpy(np.random.default_rng(5).integers(0, L, (B, Nb, C + 3)).astype(np.int32)).cuda()
+    before = per(zv)
+    hb.maxpool_points_bwd_add(B, Nb, C, L, DT[dtype], dV, idx, (Nb * (C + 3), C + 3, 1), zp, sst)
+    dv_nc = H(dV)[:, :, :C].transpose(1, 0, 2).reshape(Nb, B * C)
+    idx_nc = H(idx)[:, :, :C].transpose(1, 0, 2).reshape(Nb, B * C)
+    check(per(zv), oops.maxpool_points_bwd_add(before, dv_nc, idx_nc), TOL[dtype], "maxpool_points_bwd_add")
+    # softmax_xent_points over K = C classes
+    labels = torch.from_numpy(np.random.default_rng(6).integers(0, C, (B, Nb, L)).astype(np.int32)).cuda()
+    loss = torch.empty(B, device="cuda")
+    dl = torch.empty(Nb, B * C, L, dtype=tdt, device="cuda")
+    ws = torch.empty(hb.softmax_xent_points_workspace_bytes(B, Nb, L), dtype=torch.uint8, device="cuda")
+    hb.softmax_xent_points(B, Nb, C, L, DT[dtype], zp, sst, labels, loss, dl, dst, ws)
+    lg = per(zv).reshape(Nb, B, C, L)
+    for b in range(B):
+        rl, rd = oops.softmax_xent_points(lg[:, b], H(labels)[b])
+        assert abs(float(loss[b]) - rl) <= 1e-5 * abs(rl)
+        check(H(dl).reshape(Nb, B, C, L)[:, b], rd, TOL[dtype], "dlogits")
+
+
+def seg_probe(spec, seen):
+    """The classification test's per-call checks for the operators both arrays share, plus the
+    segmentation head's own pieces."""
+    base = in_place_probe(spec, seen)
+    B, tol = spec.B, TOL[spec.dtype]
+    ftol = 1e-5 if spec.dtype == "f32" else 2e-4
+
+    def flat(t):                          # [Nb, B, C, L] slice view -> contiguous [Nb, B*C, L]
+        return t.reshape(t.shape[0], t.shape[1] * t.shape[2], t.shape[3]) if (t is not None and t.dim() == 4) else t
+
+    def probe(op, **kw):
+        torch.cuda.synchronize()
+        kw = {k: (flat(v) if isinstance(v, torch.Tensor) else v) for k, v in kw.items()}
+        lay = kw.get("layer", "")
+        if op in ("bn_fwd", "bn_bwd"):
+            return base(op, layout="conv", **kw)
+        if op in ("conv1x1_fwd", "conv1x1_bwd", "maxpool_points"):
+            return base(op, **kw)
+        seen.append(op)
+        if op == "linear_fwd":
+            Fx = kw["x"].shape[2]
+            y = np.stack([oops.linear_fwd(H(kw["x"])[b], H(kw["w"]).reshape(B, Fx, -1)[b]) for b in range(B)])
+            check(H(kw["y"]), y, tol, f"{lay} fwd")
+        elif op == "linear_bwd":
+            Fx = kw["x"].shape[2]
+            for b in range(B):
+                dx, dw, _ = oops.linear_bwd(H(kw["x"])[b], H(kw["w"]).reshape(B, Fx, -1)[b], H(kw["dy"])[b])
+                check(H(kw["dx"])[b], dx, tol, f"{lay} dX")
+                check(H(kw["dw"]).reshape(B, Fx, -1)[b], dw, ftol, f"{lay} dW")
+        elif op == "add_sample_bias":
+            Nb, C = kw["s"].shape[1], kw["s"].shape[2]
+            s_nc = H(kw["s"]).transpose(1, 0, 2).reshape(Nb, B * C)
+            check(H(kw["y"]), oops.add_sample_bias(H(kw["z"]), s_nc), tol, "add_sample_bias")
+        elif op == "sum_points":
+            Nb, C = kw["s"].shape[1], kw["s"].shape[2]
+            check(H(kw["s"]), oops.sum_points(H(kw["x"])).reshape(Nb, B, C).transpose(1, 0, 2), tol, "sum_points")
+        elif op == "add_strided":
+            check(H(kw["y"]), H(kw["a"]) + H(kw["b"]), tol, "add_strided")
+        elif op == "maxpool_points_bwd_add":
+            Nb, C = kw["dv"].shape[1], kw["dv"].shape[2]
+            t2 = lambda a: H(a).transpose(1, 0, 2).reshape(Nb, B * C)
+            check(H(kw["dx"]), oops.maxpool_points_bwd_add(H(kw["dx0"]), t2(kw["dv"]), t2(kw["idx"])), tol, "pool bwd add")
+        elif op == "softmax_xent_points":
+            lg = H(kw["logits"])
+            Nb, L = lg.shape[0], lg.shape[2]
+            K = lg.shape[1] // B
+            for b in range(B):
+                rl, rd = oops.softmax_xent_points(lg.reshape(Nb, B, K, L)[:, b], H(kw["labels"])[b])
+                assert abs(float(kw["loss"][b]) - rl) <= 1e-5 * abs(rl)
+                check(H(kw["d"]).reshape(Nb, B, K, L)[:, b], rd, tol, "dlogits")
+        else:
+            raise AssertionError(op)
+    return probe
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_seg_every_call_in_place_and_chain(dtype):
+    """Config 2's layer list with every width divided by 8 (B=2, 3 clouds of 260 points: several
+    point tiles and a ragged one), every call checked in place; then the free-running loss and the
+    gradients against B unfused oracle runs, and Adam."""
+    from paper_2102_02344_amd.arrays import FusedPointNetSeg
+    spec = hi.seg_thin(2, 3, 260, dtype)
+    inp = hi.pointnet_seg_inputs(spec)
+    arr = FusedPointNetSeg(spec, inp)
+    seen = []
+    arr.forward_backward(seg_probe(spec, seen))
+    nconv, nh = len(spec.conv) - 1, len(spec.head) - 1
+    assert len(seen) == 2 * nconv + 1 + 1 + nh + 1 + (nh - 1) + 1 + (nh - 1) + nh + 2 + 1 + (nconv - 1) + 2 * nconv
+    states = [oseg.init_state(inp["params"][b]) for b in range(spec.B)]
+    outs = oseg.array_train_step(spec, states, inp, 1)
+    tol = CHAIN_TOL[dtype] if dtype == "bf16" else 1e-5 * (6 * nconv + 6 * nh + 8)
+    loss = arr.loss.cpu().numpy()
+    for b in range(spec.B):
+        assert abs(loss[b] - outs[b]["loss"]) <= tol * abs(outs[b]["loss"]), (b, loss[b], outs[b]["loss"])
+    if dtype == "f32":
+        wmax = {b: max(np.abs(outs[b]["grads"][n]).max() for n, _ in arr.shapes if n.endswith(".w")) for b in range(spec.B)}
+        for b in range(spec.B):
+            for name, _ in arr.shapes:
+                g = arr.param_host(arr.grad, name, b).astype(np.float64)
+                ref = outs[b]["grads"][name]
+                if name.endswith(".b") and ".bn." not in name and name != f"head{nh - 1}.b":
+                    assert np.abs(g).max() <= 1e-2 * wmax[b]          # a bias under a BatchNorm: zero up to rounding
+                    continue
+                err = np.abs(g - ref).max() / max(np.abs(ref).max(), 1e-30)
+                assert err <= tol, (name, b, err)
+        arr.adam()
+        torch.cuda.synchronize()
+        for b in range(spec.B):
+            lr = float(inp["lr"][b])
+            for name, _ in arr.shapes:
+                th = arr.param_host(arr.theta, name, b).astype(np.float64)
+                assert np.abs(th - states[b]["theta"][name]).max() <= 2.5 * lr, (name, b)
+
+
+def test_seg_fused_equals_serial_B1_on_gpu():
+    """Model 1 of the fused array equals that model run alone through the library with B = 1."""
+    import dataclasses
+    from paper_2102_02344_amd.arrays import FusedPointNetSeg
+    spec = hi.seg_thin(3, 2, 132, "bf16")
+    inp = hi.pointnet_seg_inputs(spec)
+    arr = FusedPointNetSeg(spec, inp)
+    arr.train_step()
+    s1 = dataclasses.replace(spec, B=1)
+    i1 = {k: (v[1:2] if isinstance(v, np.ndarray) and v.shape[:1] == (spec.B,) else v) for k, v in inp.items()}
+    i1["points"] = inp["points"][:, 3:6, :]
+    i1["params"] = [inp["params"][1]]
+    one = FusedPointNetSeg(s1, i1)
+    one.train_step()
+    torch.cuda.synchronize()
+    assert abs(float(arr.loss[1]) - float(one.loss[0])) <= 1e-6 * abs(float(one.loss[0]))
+    for name, _ in arr.shapes:
+        a, o = arr.param_host(arr.theta, name, 1), one.param_host(one.theta, name, 0)
+        assert np.abs(a - o).max() <= 1e-6 * max(np.abs(o).max(), 1e-3) + 2.5 * float(inp["lr"][1]) * 1e-3, name
