@@ -238,3 +238,11 @@ def adam_step(B, theta, grad, m, v, lr, beta1, beta2, eps, wd, t, decoupled_wd=F
                                 eps[b], wd[b], t, decoupled_wd)
         th[b], mo[b], vo[b] = a, c, d
     return th, mo, vo
+
+
+def adadelta_step(B, theta, grad, sq_avg, acc_delta, lr, rho, eps, wd):
+    """Arena tensors [B, P]; hyper-parameter vectors [B].  State is stored fp32."""
+    th, vo, uo = (np.empty(theta.shape, np.float32) for _ in range(3))
+    for b in range(B):
+        th[b], vo[b], uo[b] = ops.adadelta_step(theta[b], grad[b], sq_avg[b], acc_delta[b], lr[b], rho[b], eps[b], wd[b])
+    return th, vo, uo

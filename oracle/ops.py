@@ -448,3 +448,27 @@ def adam_step(theta, grad, m, v, lr: float, beta1: float, beta2: float, eps: flo
     vhat = v / (1.0 - beta2 ** t)
     theta = theta - lr * mhat / (np.sqrt(vhat) + eps)
     return theta, m, v
+
+
+# --------------------------------------------------------------------------
+# Adadelta and the step learning-rate schedule (section "Our Proposal: HFTA",
+# paragraph on optimizers and learning-rate schedulers: per-model hyper-parameter
+# vectors; Zeiler's ADADELTA with a learning-rate factor)
+# --------------------------------------------------------------------------
+def adadelta_step(theta, grad, sq_avg, acc_delta, lr: float, rho: float, eps: float, weight_decay: float):
+    """g' = g + wd*theta;  v = rho v + (1-rho) g'^2;  d = sqrt(u + eps) / sqrt(v + eps) * g';
+    u = rho u + (1-rho) d^2;  theta -= lr * d.   Returns (theta, v, u) as float64."""
+    theta, g, v, u = _f64(theta), _f64(grad), _f64(sq_avg), _f64(acc_delta)
+    lr, rho, eps, weight_decay = float(lr), float(rho), float(eps), float(weight_decay)
+    g = g + weight_decay * theta
+    v = rho * v + (1.0 - rho) * g * g
+    d = np.sqrt(u + eps) / np.sqrt(v + eps) * g
+    u = rho * u + (1.0 - rho) * d * d
+    return theta - lr * d, v, u
+
+
+def steplr(base_lr, gamma, step_size, epoch: int):
+    """Per-model step schedule: lr_b = base_lr_b * gamma_b ** floor(epoch / step_size_b)."""
+    base_lr, gamma = _f64(base_lr), _f64(gamma)
+    k = np.floor_divide(int(epoch), np.asarray(step_size, np.int64))
+    return base_lr * gamma ** k

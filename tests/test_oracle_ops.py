@@ -451,3 +451,38 @@ def test_segmentation_head_pieces():
     idx = RNG.integers(0, L, (N, C))
     out = ops.maxpool_points_bwd_add(dx, dv, idx)
     close(out, dx + ops.maxpool_points_bwd(dv, idx, L), 1e-15)
+
+
+def test_adadelta_and_steplr_vs_library_and_closed_forms():
+    """torch.optim.Adadelta / StepLR (library routines, float64) over several steps with weight
+    decay; first step from zero state in closed form; lr = 0 leaves the parameters untouched."""
+    import torch
+    P = 9
+    th0 = rnd(P)
+    grads = [rnd(P) for _ in range(4)]
+    lr, rho, eps, wd = 0.7, 0.85, 1e-6, 0.05
+    tp = torch.tensor(th0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adadelta([tp], lr=lr, rho=rho, eps=eps, weight_decay=wd)
+    th, v, u = th0.copy(), np.zeros(P), np.zeros(P)
+    for g in grads:
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        th, v, u = ops.adadelta_step(th, g, v, u, lr, rho, eps, wd)
+        close(th, tp.detach().numpy(), 1e-12)
+    g = grads[0]
+    th1, v1, u1 = ops.adadelta_step(th0, g, np.zeros(P), np.zeros(P), lr, rho, eps, 0.0)
+    d = math.sqrt(eps) / np.sqrt((1 - rho) * g * g + eps) * g
+    close(v1, (1 - rho) * g * g, 1e-14)
+    close(u1, (1 - rho) * d * d, 1e-12)
+    close(th1 - th0, -lr * d, 1e-12)
+    assert np.array_equal(ops.adadelta_step(th0, g, v, u, 0.0, rho, eps, wd)[0], th0)
+    # step schedule against the library, per-model factor and period
+    base, gam, step = np.array([0.1, 0.02, 0.5]), np.array([0.5, 0.1, 0.9]), np.array([1, 3, 4])
+    for b in range(3):
+        q = torch.nn.Parameter(torch.zeros(1))
+        o = torch.optim.SGD([q], lr=float(base[b]))
+        sch = torch.optim.lr_scheduler.StepLR(o, step_size=int(step[b]), gamma=float(gam[b]))
+        for epoch in range(10):
+            assert abs(ops.steplr(base, gam, step, epoch)[b] - o.param_groups[0]["lr"]) <= 1e-12 * base[b]
+            o.step()
+            sch.step()
