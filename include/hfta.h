@@ -305,6 +305,24 @@ int hfta_adam_step_multi(int B, int nseg, const int64_t* seg_offsets, int grad_d
                          const float* weight_decay, int step_t, int decoupled_wd, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Fused Adadelta over the same parameter-major arena, and the fused step learning-rate schedule
+ * (section "Our Proposal: HFTA", paragraph on optimizers and learning-rate schedulers: each
+ * hyper-parameter becomes a vector with one entry per model).  Arguments as hfta_adam_step_multi;
+ * square_avg and acc_delta are the two fp32 state buffers; lr, rho, eps, weight_decay: device [B].
+ *   g' = g + wd*theta;  v = rho v + (1-rho) g'^2;  d = sqrt(u + eps) / sqrt(v + eps) * g';
+ *   u = rho u + (1-rho) d^2;  theta -= lr d
+ * hfta_steplr: lr[b] = base_lr[b] * gamma[b] ^ floor(epoch / step_size[b]) (all device arrays of B
+ * entries, step_size int32 >= 1; computed in double), so a schedule step is a launch on the
+ * training stream and the optimisers read the result from device memory.
+ * ---------------------------------------------------------------------- */
+int hfta_adadelta_step_multi(int B, int nseg, const int64_t* seg_offsets, int grad_dtype,
+                             float* theta, const void* grad, float* square_avg, float* acc_delta,
+                             void* theta_lowp, const float* lr, const float* rho, const float* eps,
+                             const float* weight_decay, void* stream);
+int hfta_steplr(int B, const float* base_lr, const float* gamma, const int32_t* step_size, int epoch,
+                float* lr, void* stream);
+
+/* ------------------------------------------------------------------------
  * Support operators needed to close a training step (fusion rules table, rows
  * "ReLU", "LeakyReLU", "Tanh", "Dropout", "LayerNorm"; appendix "Fused Loss").
  * Elementwise operators work on `count` contiguous elements of any fused layout.

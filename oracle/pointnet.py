@@ -172,13 +172,18 @@ def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
 
 
 def train_step(spec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, fused_tail=False):
-    """One fwd + bwd + Adam step of one model; updates ``state`` in place.
-    hp: dict(lr, beta1, beta2, eps, wd) scalars.  Returns the forward/backward dict."""
+    """One fwd + bwd + optimiser step of one model; updates ``state`` in place.
+    hp: dict(lr, beta1, beta2, eps, wd) scalars for Adam, dict(lr, rho, eps, wd) for Adadelta.
+    Returns the forward/backward dict."""
     out = forward_backward(spec, state["theta"], points, labels, drop_mask, state["running"], fused_tail=fused_tail)
     for k in state["theta"]:
         g = ops.store(out["grads"][k], "f32")
-        th, m, v = ops.adam_step(state["theta"][k], g, state["m"][k], state["v"][k],
-                                 hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["wd"], t)
+        if "rho" in hp:     # Adadelta: the two state buffers hold the running square average and the accumulated delta
+            th, m, v = ops.adadelta_step(state["theta"][k], g, state["m"][k], state["v"][k],
+                                         hp["lr"], hp["rho"], hp["eps"], hp["wd"])
+        else:
+            th, m, v = ops.adam_step(state["theta"][k], g, state["m"][k], state["v"][k],
+                                     hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["wd"], t)
         state["theta"][k] = th.astype(np.float32)
         state["m"][k] = m.astype(np.float32)
         state["v"][k] = v.astype(np.float32)
@@ -191,7 +196,7 @@ def array_train_step(spec, states: List[dict], inp: dict, t: int, fused_tail=Fal
     """The array's reference: B separate unfused runs, one after another."""
     outs = []
     for b in range(spec.B):
-        hp = {k: float(inp[k][b]) for k in ("lr", "beta1", "beta2", "eps", "wd")}
+        hp = {k: float(inp[k][b]) for k in ("lr", "beta1", "beta2", "eps", "wd", "rho") if k in inp}
         mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
         outs.append(train_step(spec, states[b], inp["points"][:, 3 * b:3 * b + 3, :],
                                inp["labels"][b], hp, t, mask, fused_tail))

@@ -100,6 +100,17 @@ class ParamArena:
         hb.adam_step_multi(self.B, self.seg_offsets, hb.F32, self.theta, self.grad, self.m, self.v, self.lowp,
                            self.hp["lr"], self.hp["beta1"], self.hp["beta2"], self.hp["eps"], self.hp["wd"], self.t)
 
+    def adadelta(self, rho: torch.Tensor, eps: torch.Tensor):
+        """Adadelta instead of Adam (``rho``, ``eps``: device ``[B]``); the two state buffers hold
+        the running square average and the accumulated squared delta."""
+        self.t += 1
+        hb.adadelta_step_multi(self.B, self.seg_offsets, hb.F32, self.theta, self.grad, self.m, self.v, self.lowp,
+                               self.hp["lr"], rho, eps, self.hp["wd"])
+
+    def steplr(self, base_lr: torch.Tensor, gamma: torch.Tensor, step_size: torch.Tensor, epoch: int):
+        """Per-model step schedule: rewrites the device learning-rate vector the optimisers read."""
+        hb.steplr(self.B, base_lr, gamma, step_size, epoch, self.hp["lr"])
+
     def train_step(self):
         loss = self.forward_backward()
         self.adam()

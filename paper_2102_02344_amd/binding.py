@@ -58,6 +58,8 @@ _SIGS = {
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
     "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 21 + [_i, _f, _p, _sz, _p]),
+    "hfta_adadelta_step_multi": (_i, [_i, _i, _s4, _i] + [_p] * 9 + [_p]),
+    "hfta_steplr": (_i, [_i, _p, _p, _p, _i, _p, _p]),
     "hfta_add_sample_bias": (_i, [_i] * 5 + [_p] * 7),
     "hfta_sum_points": (_i, [_i] * 5 + [_p] * 5),
     "hfta_add_strided": (_i, [_i] * 5 + [_p] * 7),
@@ -375,3 +377,16 @@ def softmax_xent_points(B, Nb, K, L, dtype, logits, ls, labels, loss, dlogits, d
     wp, wb = _ws(workspace)
     _check(_lib.hfta_softmax_xent_points(B, Nb, K, L, dtype, _ptr(logits), _strides(ls), _ptr(labels), _ptr(loss),
                                          _ptr(dlogits), _strides(ds), wp, wb, _stream(stream)), "hfta_softmax_xent_points")
+
+
+def adadelta_step_multi(B, seg_offsets, grad_dtype, theta, grad, square_avg, acc_delta, theta_lowp, lr, rho, eps,
+                        weight_decay, stream=None):
+    nseg = len(seg_offsets) - 1
+    _check(_lib.hfta_adadelta_step_multi(B, nseg, _strides(seg_offsets, nseg + 1), grad_dtype, _ptr(theta), _ptr(grad),
+                                         _ptr(square_avg), _ptr(acc_delta), _ptr(theta_lowp), _ptr(lr), _ptr(rho),
+                                         _ptr(eps), _ptr(weight_decay), _stream(stream)), "hfta_adadelta_step_multi")
+
+
+def steplr(B, base_lr, gamma, step_size, epoch, lr, stream=None):
+    _check(_lib.hfta_steplr(B, _ptr(base_lr), _ptr(gamma), _ptr(step_size), epoch, _ptr(lr), _stream(stream)),
+           "hfta_steplr")

@@ -296,6 +296,53 @@ def test_adam_closed_form_and_routing(hb):
         assert np.abs(th[b] - ref).max() < 2e-6
 
 
+@pytest.mark.parametrize("gdtype,segs", [("f32", (0, 12, 40, 1064)), ("bf16", (0, 5, 31, 1000))])
+def test_adadelta_arena_and_steplr(hb, gdtype, segs):
+    """Adadelta over a parameter-major arena with per-model lr / rho / eps / weight decay (one
+    launch for all models; the second segment table has sizes that are not multiples of 4), its
+    learning rates produced on the device by the per-model step schedule."""
+    B, P = 3, segs[-1]
+    rng = np.random.default_rng(91)
+    base = np.array([1.0, 0.5, 0.0], np.float32)          # model 2: lr = 0, parameters must not move
+    gam = np.array([0.5, 0.1, 0.9], np.float32)
+    step = np.array([1, 2, 3], np.int32)
+    rho = np.array([0.9, 0.8, 0.95], np.float32)
+    eps = np.array([1e-6, 1e-5, 1e-6], np.float32)
+    wd = np.array([0.0, 0.05, 0.1], np.float32)
+    # arena layout: segment j holds [B][n_j]
+    def to_arena(a):                                       # [B, P] -> flat parameter-major
+        return np.concatenate([a[:, segs[j]:segs[j + 1]].reshape(-1) for j in range(len(segs) - 1)])
+    def from_arena(f):
+        out = np.empty((B, P), np.float64)
+        o = 0
+        for j in range(len(segs) - 1):
+            n = segs[j + 1] - segs[j]
+            out[:, segs[j]:segs[j + 1]] = f[o:o + B * n].reshape(B, n)
+            o += B * n
+        return out
+    th = (hi.normal(92, (B, P)) * 0.1).astype(np.float32)
+    TH = dev(to_arena(th))
+    V_, U_ = dev(np.zeros(B * P, np.float32)), dev(np.zeros(B * P, np.float32))
+    LP = empty((B * P,), torch.bfloat16)
+    LR = empty((B,), torch.float32)
+    Hd = {k: dev(a) for k, a in dict(base=base, gam=gam, rho=rho, eps=eps, wd=wd).items()}
+    STEP = torch.from_numpy(step).cuda()
+    th_r, v_r, u_r = th.astype(np.float64), np.zeros((B, P)), np.zeros((B, P))
+    for epoch in range(4):
+        hb.steplr(B, Hd["base"], Hd["gam"], STEP, epoch, LR)
+        lr_r = oops.steplr(base, gam, step, epoch)
+        assert np.abs(host(LR) - lr_r).max() <= 1e-6 * max(lr_r.max(), 1e-30)
+        g = hi.normal(100 + epoch, (B, P), gdtype)
+        hb.adadelta_step_multi(B, list(segs), DT[gdtype], TH, dev(to_arena(g), gdtype), V_, U_, LP, LR, Hd["rho"],
+                               Hd["eps"], Hd["wd"])
+        th_r, v_r, u_r = oa.adadelta_step(B, th_r, g, v_r, u_r, host(LR), rho, eps, wd)
+    check(from_arena(host(TH)), th_r, 1e-5, "theta")
+    check(from_arena(host(V_)), v_r, 1e-5, "square_avg")
+    check(from_arena(host(U_)), u_r, 2e-5, "acc_delta")
+    assert np.array_equal(from_arena(host(TH))[2], th[2].astype(np.float64))     # lr = 0
+    assert torch.equal(LP, TH.to(torch.bfloat16))
+
+
 # ------------------------------------------------------------------ support ops
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_activations_dropout(hb, dtype):
