@@ -122,6 +122,8 @@ def kernel_label(name, a):
         B, Nb, Ci, Co, L, dt = a[:6]
         k = "gemm_pf_kernel" if dt == 1 else "gemm_kernel"
         if a[11] is not None:
+            if dt == 1 and Co <= 128 and Co % 8 == 0 and Ci >= 64 and L % 4 == 0 and a[15] is not None:
+                return "conv1x1_stream_kernel(dX)"
             return ("gemm_big_kernel" if dt == 1 and big_gemm(B * Nb, Ci, L, Co) else k) + "(dX)"
         return k + "(dW)+splitk_reduce_kernel"
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):

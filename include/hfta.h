@@ -106,7 +106,13 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
  *           dW[b,o,c]   = sum_{n,l} dY[b,n,o,l] X[b,n,c,l]   (fp32; NULL = skip)
  *           dbias[b,o]  = sum_{n,l} dY[b,n,o,l]              (fp32; NULL = skip)
  * The reduction over n and l is split across workgroups; partial sums go to
- * the workspace and are added in a fixed order (bit-reproducible). */
+ * the workspace and are added in a fixed order (bit-reproducible).  With a
+ * 256-byte aligned workspace of hfta_conv1x1_bwd_workspace_bytes the data
+ * gradient of a narrow bf16 layer (Co <= 128) runs as a streaming k=1
+ * convolution of dY with W^T, which is written to the workspace first; with
+ * a smaller or NULL workspace dX takes the general GEMM path (same result up
+ * to fp32 summation order).  EWORKSPACE only if dW is asked for and its
+ * partial sums do not fit. */
 size_t hfta_conv1x1_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
 int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                      const void* X, const int64_t xs[4], const void* W,

@@ -367,7 +367,7 @@ class FusedPointNetCls(ParamArena):
             # gradient's split-K reduction), so a caller can time them separately
             if i > 0:
                 hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, self.w(k + ".w"), dz, cs,
-                               dxin, _cs(B, ci, L), None, None, None)
+                               dxin, _cs(B, ci, L), None, None, self.ws)
             hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), None, dz, cs,
                            None, None, self.g(k + ".w"), None, self.ws)
             P("conv1x1_bwd", layer=k, x=xin, w=self.w(k + ".w"), dy=dz.view(Nb, B * co, L),
@@ -816,7 +816,7 @@ class FusedPointNetSeg(ParamArena):
                 d, cur = dz, cur ^ 1
             hin, hs = (self.cat, cst) if i == 0 else (self.ah[i - 1], _cs(B, ci, L))
             dx, dxs = (self.dcat, cst) if i == 0 else (self.dbuf[cur ^ 1][:Nb * B * ci * L], _cs(B, ci, L))
-            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, self.w(k + ".w"), d, cs, dx, dxs, None, None, None)
+            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, self.w(k + ".w"), d, cs, dx, dxs, None, None, self.ws)
             own_db = self.g(k + ".b") if i == self.nh - 1 else None      # else from the BatchNorm backward
             hb.conv1x1_bwd(B, Nb, ci, co, L, dt, hin, hs, None, d, cs, None, None, self.g(k + ".w"), own_db, self.ws)
             P("conv1x1_bwd", layer=k, x=hin, w=self.w(k + ".w"), dy=d.view(Nb, B * co, L),
@@ -857,7 +857,7 @@ class FusedPointNetSeg(ParamArena):
                 xinv = self._slice(self.cat, i - 1)[1]
                 dnext = self.dbuf[1][:Nb * B * ci * L]
                 hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, self.w(k + ".w"), dz, cs, dnext, _cs(B, ci, L),
-                               None, None, None)
+                               None, None, self.ws)
             else:
                 xin, xs, xinv, dnext = self.points, _cs(B, 3, L), self.points, None
             hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, xs, None, dz, cs, None, None, self.g(k + ".w"), None, self.ws)

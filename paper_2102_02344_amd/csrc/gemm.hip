@@ -5,13 +5,21 @@
 namespace hfta {
 
 // Sum split-K partials in a fixed order: out[i] = sum_s partial[s][i].
-__global__ void splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out,
-                                     int64_t count, int splits) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= count) return;
+// out[i] = sum over the splits of partial[k][i] in a fixed order: thread (i, q) adds the splits
+// k = q, q+4, ... (several loads in flight), the four quarter sums are combined as (0+1)+(2+3).
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out,
+                                                            int64_t count, int splits) {
+  __shared__ float sh[4][64];
+  const int q = threadIdx.x >> 6, li = threadIdx.x & 63;
+  const int64_t i = (int64_t)blockIdx.x * 64 + li;
   float s = 0.f;
-  for (int k = 0; k < splits; ++k) s += partial[(int64_t)k * count + i];
-  out[i] = s;
+  if (i < count) {
+#pragma unroll 8
+    for (int k = q; k < splits; k += 4) s += partial[(int64_t)k * count + i];
+  }
+  sh[q][li] = s;
+  __syncthreads();
+  if (q == 0 && i < count) out[i] = (sh[0][li] + sh[1][li]) + (sh[2][li] + sh[3][li]);
 }
 
 int gemm_big_launch(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t st);
@@ -166,7 +174,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   if (rc != HFTA_OK) return rc;
   if (splits > 1) {
     const int64_t count = G * (int64_t)d.M * d.N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st,
                        d.partial, reinterpret_cast<float*>(d.C), count, splits);
     return launch_status();
   }

@@ -13,6 +13,18 @@ using namespace hfta;
 namespace {
 
 // dbias of the fused Linear: column sums of dY[b] ([M][Fy]); 64 columns x 4 row slices per block.
+// Wt[b][c][o] = W[b][o][c] (a few tens of KB per model)
+__global__ __launch_bounds__(256) void transpose_w_kernel(const bf16_raw* __restrict__ W, bf16_raw* __restrict__ Wt,
+                                                          int Co, int Ci, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int o = (int)(i % Co);
+  const int64_t bc = i / Co;
+  const int c = (int)(bc % Ci);
+  const int64_t b = bc / Ci;
+  Wt[i] = W[(b * Co + o) * Ci + c];
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ dY, float* __restrict__ out,
                                                     int M, int Fy) {
@@ -232,11 +244,19 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
   return gemm_launch(d, as_stream(stream));
 }
 
+// The data gradient of a narrow layer (Co <= 128) is a k=1 convolution of dY with the transposed
+// weights: it takes the streaming forward kernel once W^T [B][Ci][Co] has been written to the workspace.
+static bool dx_streams(int Ci, int Co, int L, int dtype) {
+  return dtype == HFTA_BF16 && Co <= 128 && Co % 8 == 0 && Ci >= 64 && L % 4 == 0;
+}
+static size_t wt_offset(size_t partial_bytes) { return (partial_bytes + 255) & ~(size_t)255; }
+
 size_t hfta_conv1x1_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype) {
   if (check_conv1x1(B, Nb, Ci, Co, L, dtype) != HFTA_OK) return 0;
   const int64_t unit[4] = {(int64_t)Ci * L, (int64_t)B * Ci * L, L, 1};
   GemmDesc d = conv_dw_desc(B, Nb, Ci, Co, L, dtype, nullptr, unit, nullptr, unit, nullptr);
-  return gemm_partial_bytes(d, gemm_pick_splits(d));
+  const size_t part = gemm_partial_bytes(d, gemm_pick_splits(d));
+  return dx_streams(Ci, Co, L, dtype) ? wt_offset(part) + (size_t)B * Ci * Co * 2 : part;
 }
 
 int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
@@ -256,7 +276,21 @@ int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
     if (need > 0 && (!workspace || ws_bytes < need)) return HFTA_EWORKSPACE;
     dw.partial = reinterpret_cast<float*>(workspace);
   }
-  if (dX) {
+  bool dx_done = false;
+  if (dX && dx_streams(Ci, Co, L, dtype) && workspace) {
+    const size_t off = wt_offset(dW ? gemm_partial_bytes(dw, dw.splits) : 0);
+    const size_t bytes = (size_t)B * Ci * Co * 2;
+    if (ws_bytes >= off + bytes && reinterpret_cast<uintptr_t>(workspace) % 256 == 0) {
+      bf16_raw* wt = reinterpret_cast<bf16_raw*>(reinterpret_cast<unsigned char*>(workspace) + off);
+      const int64_t n = (int64_t)B * Ci * Co;
+      hipLaunchKernelGGL(transpose_w_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                         (const bf16_raw*)W, wt, Co, Ci, n);
+      rc = hfta::conv1x1_stream_fwd(B, Nb, Co, Ci, L, dY, dys, wt, nullptr, dX, dxs, HFTA_ACT_NONE, 0.f, st);
+      if (rc == HFTA_OK) dx_done = true;
+      else if (rc != HFTA_EUNSUPPORTED) return rc;
+    }
+  }
+  if (dX && !dx_done) {
     GemmDesc d = base_desc(dtype);
     d.A = W; d.Bm = dY; d.C = dX;
     d.M = Ci; d.N = L; d.K = Co; d.G0 = B; d.G1 = Nb;
