@@ -88,6 +88,8 @@ def kernel_label(name, a):
         return f"{name}_{lay}_kernel"
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
+        if dt == 1 and Ci <= 4 and L % 4 == 0:
+            return "conv1x1_tinyk_kernel"
         if dt == 1 and Ci <= 128 and Ci % 8 == 0 and Co >= 64 and L % 4 == 0:
             return "conv1x1_stream_kernel"
         if dt == 1 and big_gemm(B * Nb, Co, L, Ci):
@@ -129,9 +131,9 @@ def kernel_label(name, a):
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
     if name == "conv1x1_bn_maxpool_fwd":
-        return "conv1x1_bn_maxpool_fwd: fbp_main_kernel + gemm_pf_kernel(gram) + 3 small"
+        return "conv1x1_bn_maxpool_fwd: fbp_main_kernel + gram_kernel + 4 small"
     if name == "conv1x1_bn_maxpool_bwd":
-        return "conv1x1_bn_maxpool_bwd: cbp_dx_kernel + 5 small" + ("" if a[13] is not None else " + gemm_pf_kernel(gram)")
+        return "conv1x1_bn_maxpool_bwd: cbp_dx_kernel + 5 small" + ("" if a[13] is not None else " + gram_kernel")
     return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",
             "adam_step_multi": "adam_multi_kernel"}[name]
 

@@ -84,6 +84,121 @@ __global__ __launch_bounds__(64) void cbp_coef_kernel(CbpArgs p) {
   }
 }
 
+// ---- XX[b] = sum over (n, l) of x x^T, the Gram matrix of the layer input ------------------------
+// One workgroup accumulates the whole Ci x Ci matrix (Ci <= 128) over its share of 64-point tiles:
+// the tile is loaded ONCE (8-byte pieces, points contiguous = the contraction index), parked in one
+// of two LDS buffers, and serves as both operands of the matrix instruction; the next tile is in
+// flight in registers meanwhile.  Per-workgroup partial matrices are added in a fixed order by
+// gram_reduce_kernel.  HBM-bound: x read once.
+struct GramArgs {
+  const bf16_raw* X; float* partial; float* XX;
+  int64_t xsb, xsn, xsc;
+  int Nb, Ci, L, tiles_k, chunks;
+  uint32_t x_extent;
+};
+
+__global__ __launch_bounds__(GEMM_THREADS) void gram_kernel(GramArgs p) {
+  constexpr int GP = 64 * 2 + 16;                        // bytes per LDS row: 64 points + pad
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][128 * GP];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int b = blockIdx.y, chunk = blockIdx.x;
+  const int total = p.Nb * p.tiles_k;
+  const int t0 = (int)((int64_t)total * chunk / p.chunks), t1 = (int)((int64_t)total * (chunk + 1) / p.chunks);
+  const int row = t >> 4, piece = t & 15;                // 16 rows x 16 pieces per pass, 8 passes
+  uint2 q[8];
+  auto load = [&](int tile) {
+    const int n = tile / p.tiles_k, l = (tile - n * p.tiles_k) * 64 + piece * 4;
+    const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + b * p.xsb + n * p.xsn, p.x_extent);
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+      const int ci = row + 16 * h;
+      const bool ok = tile < t1 && ci < p.Ci && l + 4 <= p.L;
+      const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? (uint32_t)ci * (uint32_t)(p.xsc * 2) + (uint32_t)l * 2u : PF_OOB), 0, 0);
+      q[h] = make_uint2(v.x, v.y);
+    }
+  };
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const int r = lane & 31, gsel = lane >> 5;
+  load(t0);
+  for (int tile = t0; tile < t1; ++tile) {
+    unsigned char* buf = smem[(tile - t0) & 1];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) *reinterpret_cast<uint2*>(buf + (row + 16 * h) * GP + piece * 8) = q[h];
+    __syncthreads();                                     // the other buffer was last read one step ago
+    load(tile + 1);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      bf16x8_t a[2], bb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[i] = *reinterpret_cast<const bf16x8_t*>(buf + (wm * 64 + i * 32 + r) * GP + (2 * s + gsel) * 16);
+        bb[i] = *reinterpret_cast<const bf16x8_t*>(buf + (wn * 64 + i * 32 + r) * GP + (2 * s + gsel) * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb[j], a[i], acc[i][j], 0, 0, 0);
+    }
+  }
+  // acc[i][j][4q+e]: column (from the first operand) wn*64 + j*32 + 8q + 4*gsel + e, row (second operand) wm*64 + i*32 + r
+  float* out = p.partial + ((int64_t)chunk * gridDim.y + b) * p.Ci * p.Ci;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int ci = wm * 64 + i * 32 + r;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int cj = wn * 64 + j * 32 + 8 * (v >> 2) + 4 * gsel + (v & 3);
+        if (ci < p.Ci && cj < p.Ci) out[(int64_t)ci * p.Ci + cj] = acc[i][j][v];
+      }
+  }
+}
+
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const float* __restrict__ partial, float* __restrict__ XX,
+                                                          int64_t count, int chunks) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;          // four interleaved sums, then (0+1)+(2+3): a fixed order
+  int k = 0;
+  for (; k + 4 <= chunks; k += 4) {
+    s0 += partial[(int64_t)k * count + i];
+    s1 += partial[(int64_t)(k + 1) * count + i];
+    s2 += partial[(int64_t)(k + 2) * count + i];
+    s3 += partial[(int64_t)(k + 3) * count + i];
+  }
+  for (; k < chunks; ++k) s0 += partial[(int64_t)k * count + i];
+  XX[i] = (s0 + s1) + (s2 + s3);
+}
+
+int gram_chunks(int B, int Nb, int L) {
+  const int total = Nb * ((L + 63) / 64);
+  int c = (512 + B - 1) / B;
+  if (c > total) c = total;
+  return c < 1 ? 1 : c;
+}
+size_t gram_partial_bytes(int B, int Nb, int Ci, int L) { return (size_t)gram_chunks(B, Nb, L) * B * Ci * Ci * 4; }
+
+// XX[b][ci][cj] for all models; `partial` holds gram_partial_bytes
+int gram_launch(int B, int Nb, int Ci, int L, const void* X, const int64_t xs[4], float* XX, float* partial,
+                uint32_t x_extent, hipStream_t st) {
+  GramArgs g{(const bf16_raw*)X, partial, XX, xs[0], xs[1], xs[2], Nb, Ci, L, (L + 63) / 64, gram_chunks(B, Nb, L), x_extent};
+  hipLaunchKernelGGL(gram_kernel, dim3((unsigned)g.chunks, (unsigned)B), dim3(GEMM_THREADS), 0, st, g);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  const int64_t count = (int64_t)B * Ci * Ci;
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, (const float*)partial, XX,
+                     count, g.chunks);
+  return launch_status();
+}
+
 // ---- argmax positions of one (model, sample) sorted by point, ties in channel order ------------
 // key = point << 10 | channel (Co <= 1024, L < 2^21: checked on the host); bitonic sort in LDS.
 // toff[tile] = first sorted position whose point lies in 128-point tile `tile` or later.
@@ -813,17 +928,6 @@ size_t saved_floats(int B, int Ci, int Co) { return (size_t)B * ((size_t)Ci * Ci
 
 struct CbpLayout { size_t chan, p0, p1, s, XX, SX, negG, v, xg, SXpart, skey, sval, toff, part, total; };
 
-GemmDesc gram_desc(int B, int Nb, int Ci, int L, const void* X, const int64_t xs[4], float* XX) {
-  GemmDesc d{};
-  d.A = X; d.Bm = X; d.C = XX;
-  d.M = Ci; d.N = Ci; d.K = L; d.S = Nb; d.G0 = B; d.G1 = 1;
-  d.a_kc = true; d.a_ld = xs[2]; d.a_ss = xs[1]; d.a_g0 = xs[0];
-  d.b_kc = true; d.b_ld = xs[2]; d.b_ss = xs[1]; d.b_g0 = xs[0];
-  d.c_ld = Ci; d.c_g0 = (int64_t)Ci * Ci;
-  d.act = HFTA_ACT_NONE; d.dtype = HFTA_BF16; d.out_f32 = true; d.splits = 1;
-  return d;
-}
-
 FbpLayout fbp_layout(int B, int Nb, int Ci, int Co, int L, bool own_moments) {
   FbpLayout w{};
   size_t off = 0;
@@ -833,9 +937,7 @@ FbpLayout fbp_layout(int B, int Nb, int Ci, int Co, int L, bool own_moments) {
   w.pmax = take((size_t)B * Nb * tiles * Co * 4);
   w.pidx = take((size_t)B * Nb * tiles * Co * 4);
   w.moments = take(own_moments ? saved_floats(B, Ci, Co) * 4 : 0);
-  const int64_t unit[4] = {(int64_t)Ci * L, (int64_t)B * Ci * L, L, 1};
-  GemmDesc d = gram_desc(B, Nb, Ci, L, nullptr, unit, nullptr);
-  w.part = take(gemm_partial_bytes(d, gemm_pick_splits(d)));
+  w.part = take(gram_partial_bytes(B, Nb, Ci, L));
   w.total = off;
   return w;
 }
@@ -857,9 +959,7 @@ CbpLayout cbp_layout(int B, int Nb, int Ci, int Co, int L) {
   w.skey = take((size_t)B * Nb * Co * 4);
   w.sval = take((size_t)B * Nb * Co * 4);
   w.toff = take((size_t)B * Nb * ((L + 127) / 128 + 1) * 4);
-  const int64_t unit[4] = {(int64_t)Ci * L, (int64_t)B * Ci * L, L, 1};
-  GemmDesc d = gram_desc(B, Nb, Ci, L, nullptr, unit, nullptr);
-  w.part = take(gemm_partial_bytes(d, gemm_pick_splits(d)));
+  w.part = take(gram_partial_bytes(B, Nb, Ci, L));
   w.total = off;
   return w;
 }
@@ -923,11 +1023,8 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   }
   hipLaunchKernelGGL(cbp_coef_kernel, dim3((unsigned)Co, (unsigned)B), dim3(64), 0, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
-  if (!saved_moments) {          // Gram matrix of the layer input: XX[b] = sum_{n,l} x x^T, through the batched GEMM core
-    GemmDesc g = gram_desc(B, Nb, Ci, L, X, xs, a.XX);
-    g.splits = gemm_pick_splits(g);
-    g.partial = (float*)(ws + lay.part);
-    const int rc = gemm_launch(g, st);
+  if (!saved_moments) {          // Gram matrix of the layer input: XX[b] = sum_{n,l} x x^T
+    const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, st);
     if (rc != HFTA_OK) return rc;
   }
   const int T32 = (Ci + 31) / 32;
@@ -992,10 +1089,7 @@ int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   a.SXpart = (float*)(ws + lay.SXpart); a.pmax = (float*)(ws + lay.pmax); a.pidx = (int*)(ws + lay.pidx);
   a.x_extent = (uint32_t)x_ext; a.w_extent = (uint32_t)w_ext;
 
-  GemmDesc g = gram_desc(B, Nb, Ci, L, X, xs, a.XX);
-  g.splits = gemm_pick_splits(g);
-  g.partial = (float*)(ws + lay.part);
-  const int rc = gemm_launch(g, st);
+  const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, st);
   if (rc != HFTA_OK) return rc;
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
   if (Ci <= 64) hipLaunchKernelGGL(fbp_main_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);

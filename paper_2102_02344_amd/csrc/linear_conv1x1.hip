@@ -13,6 +13,50 @@ using namespace hfta;
 namespace {
 
 // dbias of the fused Linear: column sums of dY[b] ([M][Fy]); 64 columns x 4 row slices per block.
+// Forward of a k=1 convolution with at most 4 input channels (the point coordinates): no matrix
+// instruction pays for K = 3.  A thread owns four consecutive points, keeps their Ci inputs in
+// registers and walks the output channels; consecutive lanes write consecutive 8-byte pieces of an
+// output row.  HBM-bound: Co rows written once.
+struct TinyKArgs {
+  const bf16_raw* X; const bf16_raw* W; const bf16_raw* bias; bf16_raw* Y;
+  int64_t xsb, xsn, xsc, ysb, ysn, ysc;
+  int Ci, Co, L, act;
+  float slope;
+};
+__global__ __launch_bounds__(256) void conv1x1_tinyk_kernel(TinyKArgs p) {
+  const int n = blockIdx.y, b = blockIdx.z;
+  const int l = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (l >= p.L) return;
+  const bf16_raw* x = p.X + b * p.xsb + n * p.xsn + l;
+  float xv[4][4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    uint2 raw = make_uint2(0u, 0u);
+    if (c < p.Ci) raw = *reinterpret_cast<const uint2*>(x + c * p.xsc);
+    xv[c][0] = __uint_as_float(raw.x << 16); xv[c][1] = __uint_as_float(raw.x & 0xffff0000u);
+    xv[c][2] = __uint_as_float(raw.y << 16); xv[c][3] = __uint_as_float(raw.y & 0xffff0000u);
+  }
+  const bf16_raw* w = p.W + (int64_t)b * p.Co * p.Ci;
+  bf16_raw* y = p.Y + b * p.ysb + n * p.ysn + l;
+  for (int o = 0; o < p.Co; ++o) {
+    float acc[4];
+    const float bo = p.bias ? bf16_to_f32(p.bias[(int64_t)b * p.Co + o]) : 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (c < p.Ci) {
+        const float wc = bf16_to_f32(w[o * p.Ci + c]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = fmaf(wc, xv[c][e], acc[e]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] = apply_act(acc[e] + bo, p.act, p.slope);
+    *reinterpret_cast<uint2*>(y + o * p.ysc) = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
+  }
+}
+
 // Wt[b][c][o] = W[b][o][c] (a few tens of KB per model)
 __global__ __launch_bounds__(256) void transpose_w_kernel(const bf16_raw* __restrict__ W, bf16_raw* __restrict__ Wt,
                                                           int Co, int Ci, int64_t n) {
@@ -229,6 +273,16 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
   if (rc != HFTA_OK) return rc;
   if (!X || !W || !Y || !xs || !ys || !valid_act(act)) return HFTA_EINVAL;
   if (xs[3] != 1 || ys[3] != 1) return HFTA_EUNSUPPORTED;
+  auto al8 = [](const void* q, const int64_t* st) {
+    return reinterpret_cast<uintptr_t>(q) % 8 == 0 && st[0] % 4 == 0 && st[1] % 4 == 0 && st[2] % 4 == 0;
+  };
+  if (dtype == HFTA_BF16 && Ci <= 4 && L % 4 == 0 && al8(X, xs) && al8(Y, ys) && Nb <= 65535 && B <= 65535) {
+    TinyKArgs a{(const bf16_raw*)X, (const bf16_raw*)W, (const bf16_raw*)bias, (bf16_raw*)Y, xs[0], xs[1], xs[2],
+                ys[0], ys[1], ys[2], Ci, Co, L, act, act_slope};
+    dim3 grid((unsigned)((L / 4 + 255) / 256), (unsigned)Nb, (unsigned)B);
+    hipLaunchKernelGGL(conv1x1_tinyk_kernel, grid, dim3(256), 0, as_stream(stream), a);
+    return launch_status();
+  }
   if (dtype == HFTA_BF16) {   // wide layer, few input channels: streaming kernel
     rc = hfta::conv1x1_stream_fwd(B, Nb, Ci, Co, L, X, xs, W, bias, Y, ys, act, act_slope, as_stream(stream));
     if (rc != HFTA_EUNSUPPORTED) return rc;

@@ -82,7 +82,8 @@ def test_linear_identity_and_B1(hb):
 # ------------------------------------------------------------------ conv1x1
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Nb,Ci,Co,L", [(3, 2, 70, 150, 300), (2, 3, 3, 64, 250), (2, 2, 128, 40, 129),
-                                          (2, 4, 64, 64, 500)])
+                                          (2, 4, 64, 64, 500), (2, 3, 3, 64, 1300), (3, 2, 4, 24, 132),
+                                          (2, 2, 128, 64, 260)])
 def test_conv1x1_fwd_bwd(hb, dtype, B, Nb, Ci, Co, L):
     print(f"conv1x1 {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} L={L}", flush=True)
     x = hi.normal(11, (Nb, B * Ci, L), dtype)
