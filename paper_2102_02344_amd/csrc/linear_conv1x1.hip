@@ -24,7 +24,15 @@ struct TinyKArgs {
   float slope;
 };
 __global__ __launch_bounds__(256) void conv1x1_tinyk_kernel(TinyKArgs p) {
+  __shared__ float wl[256][4];                           // Co <= 256 (host): weights of the model, then its bias
+  __shared__ float bl[256];
   const int n = blockIdx.y, b = blockIdx.z;
+  for (int o = threadIdx.x; o < p.Co; o += 256) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) wl[o][c] = c < p.Ci ? bf16_to_f32(p.W[((int64_t)b * p.Co + o) * p.Ci + c]) : 0.f;
+    bl[o] = p.bias ? bf16_to_f32(p.bias[(int64_t)b * p.Co + o]) : 0.f;
+  }
+  __syncthreads();
   const int l = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (l >= p.L) return;
   const bf16_raw* x = p.X + b * p.xsb + n * p.xsn + l;
@@ -36,21 +44,19 @@ __global__ __launch_bounds__(256) void conv1x1_tinyk_kernel(TinyKArgs p) {
     xv[c][0] = __uint_as_float(raw.x << 16); xv[c][1] = __uint_as_float(raw.x & 0xffff0000u);
     xv[c][2] = __uint_as_float(raw.y << 16); xv[c][3] = __uint_as_float(raw.y & 0xffff0000u);
   }
-  const bf16_raw* w = p.W + (int64_t)b * p.Co * p.Ci;
   bf16_raw* y = p.Y + b * p.ysb + n * p.ysn + l;
+#pragma unroll 4
   for (int o = 0; o < p.Co; ++o) {
     float acc[4];
-    const float bo = p.bias ? bf16_to_f32(p.bias[(int64_t)b * p.Co + o]) : 0.f;
+    const float4 wo = *reinterpret_cast<const float4*>(wl[o]);
+    const float wc[4] = {wo.x, wo.y, wo.z, wo.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[e] = 0.f;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      if (c < p.Ci) {
-        const float wc = bf16_to_f32(w[o * p.Ci + c]);
+    for (int c = 0; c < 4; ++c)                          // channels past Ci: weight and input are zero
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = fmaf(wc, xv[c][e], acc[e]);
-      }
-    }
+      for (int e = 0; e < 4; ++e) acc[e] = fmaf(wc[c], xv[c][e], acc[e]);
+    const float bo = bl[o];
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[e] = apply_act(acc[e] + bo, p.act, p.slope);
     *reinterpret_cast<uint2*>(y + o * p.ysc) = make_uint2(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]));
@@ -276,7 +282,7 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
   auto al8 = [](const void* q, const int64_t* st) {
     return reinterpret_cast<uintptr_t>(q) % 8 == 0 && st[0] % 4 == 0 && st[1] % 4 == 0 && st[2] % 4 == 0;
   };
-  if (dtype == HFTA_BF16 && Ci <= 4 && L % 4 == 0 && al8(X, xs) && al8(Y, ys) && Nb <= 65535 && B <= 65535) {
+  if (dtype == HFTA_BF16 && Ci <= 4 && Co <= 256 && L % 4 == 0 && al8(X, xs) && al8(Y, ys) && Nb <= 65535 && B <= 65535) {
     TinyKArgs a{(const bf16_raw*)X, (const bf16_raw*)W, (const bf16_raw*)bias, (bf16_raw*)Y, xs[0], xs[1], xs[2],
                 ys[0], ys[1], ys[2], Ci, Co, L, act, act_slope};
     dim3 grid((unsigned)((L / 4 + 255) / 256), (unsigned)Nb, (unsigned)B);
