@@ -271,6 +271,81 @@ def pointnet_seg_inputs(spec: PointNetSegSpec, seed: Optional[int] = None) -> Di
 
 
 # --------------------------------------------------------------------------
+# Transformer-encoder language-model fused array (the paper's secondary Transformer workload;
+# synthetic token streams stand in for its text corpus)
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class TransformerSpec:
+    name: str
+    B: int
+    N: int                  # sequences per model per step
+    S: int                  # tokens per sequence
+    E: int                  # model width
+    heads: int
+    F: int                  # feed-forward width
+    layers: int
+    V: int                  # vocabulary size
+    dtype: str
+    lr_range: Tuple[float, float] = (1e-4, 1e-3)
+    config_index: int = 5
+
+    @property
+    def Nb(self) -> int:    # samples (sequences) per model per step
+        return self.N
+
+
+def spec_t0(B: int = 8, N: int = 32, S: int = 64, E: int = 256, heads: int = 4, F: int = 1024, layers: int = 2,
+            V: int = 8192, dtype: str = "bf16") -> TransformerSpec:
+    return TransformerSpec(name=f"t0_transformer_lm_B{B}_{dtype}", B=B, N=N, S=S, E=E, heads=heads, F=F, layers=layers,
+                           V=V, dtype=dtype)
+
+
+def transformer_param_shapes(spec: TransformerSpec) -> List[Tuple[str, Tuple[int, ...]]]:
+    """Per-model parameters in arena order; Linear weights are [Fx, Fy] (baddbmm orientation)."""
+    E, F, V = spec.E, spec.F, spec.V
+    out: List[Tuple[str, Tuple[int, ...]]] = [("emb", (V, E))]
+    for i in range(spec.layers):
+        k = f"l{i}"
+        out += [(k + ".in.w", (E, 3 * E)), (k + ".in.b", (3 * E,)), (k + ".out.w", (E, E)), (k + ".out.b", (E,)),
+                (k + ".ln1.w", (E,)), (k + ".ln1.b", (E,)), (k + ".ff1.w", (E, F)), (k + ".ff1.b", (F,)),
+                (k + ".ff2.w", (F, E)), (k + ".ff2.b", (E,)), (k + ".ln2.w", (E,)), (k + ".ln2.b", (E,))]
+    out += [("dec.w", (E, V)), ("dec.b", (V,))]
+    return out
+
+
+def transformer_inputs(spec: TransformerSpec, seed: Optional[int] = None, perturb_ln: bool = False) -> Dict[str, object]:
+    """tokens, targets int32 [B, N, S] (targets = the next token of a stream of N*S+1 uniform tokens);
+    params; lr, beta1, beta2, eps, wd [B]."""
+    seed = config_seed(spec.config_index) if seed is None else seed
+    rngs = model_streams(seed, spec.B)
+    B, N, S = spec.B, spec.N, spec.S
+    tokens = np.empty((B, N, S), np.int32)
+    targets = np.empty((B, N, S), np.int32)
+    params = []
+    lr = np.empty(B, np.float32)
+    for b, rng in enumerate(rngs):
+        stream = rng.integers(0, spec.V, size=N * S + 1)
+        tokens[b] = stream[:-1].reshape(N, S)
+        targets[b] = stream[1:].reshape(N, S)
+        p = {}
+        for name, shape in transformer_param_shapes(spec):
+            if name == "emb":
+                p[name] = rng.uniform(-0.1, 0.1, size=shape).astype(np.float32)
+            elif ".ln" in name:
+                base = 1.0 if name.endswith(".w") else 0.0
+                p[name] = (base + (0.1 * rng.standard_normal(shape) if perturb_ln else 0.0)) * np.ones(shape)
+                p[name] = p[name].astype(np.float32)
+            elif name.endswith(".w"):
+                p[name] = uniform_fan_in(rng, shape, shape[0], 3.0).astype(np.float32)
+            else:
+                p[name] = np.zeros(shape, np.float32) if not perturb_ln else (0.05 * rng.standard_normal(shape)).astype(np.float32)
+        params.append(p)
+        lr[b] = log_uniform(rng, *spec.lr_range)
+    return dict(tokens=tokens, targets=targets, params=params, lr=lr, beta1=np.full(B, 0.9, np.float32),
+                beta2=np.full(B, 0.999, np.float32), eps=np.full(B, 1e-8, np.float32), wd=np.zeros(B, np.float32))
+
+
+# --------------------------------------------------------------------------
 # operator-level cases (shapes of the other workloads)
 # --------------------------------------------------------------------------
 def normal(seed: int, shape: Sequence[int], dtype: str = "f32", scale: float = 1.0) -> np.ndarray:

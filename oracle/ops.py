@@ -472,3 +472,77 @@ def steplr(base_lr, gamma, step_size, epoch: int):
     base_lr, gamma = _f64(base_lr), _f64(gamma)
     k = np.floor_divide(int(epoch), np.asarray(step_size, np.int64))
     return base_lr * gamma ** k
+
+
+# --------------------------------------------------------------------------
+# Embedding and scaled-dot-product multi-head attention (fusion rules table rows
+# "Embedding" and, built from the Linear rule plus per-model batched products,
+# "MultiheadAttention"; the Transformer workloads of section "Methodology")
+# --------------------------------------------------------------------------
+def embedding_fwd(table, idx, scale: float = 1.0, pos=None):
+    """table:[V,E], idx:[R] int -> scale * table[idx] (+ pos[r % len(pos)] if given):[R,E]."""
+    y = scale * _f64(table)[np.asarray(idx, np.int64)]
+    if pos is not None:
+        pos = _f64(pos)
+        y = y + pos[np.arange(y.shape[0]) % pos.shape[0]]
+    return y
+
+
+def embedding_bwd(dy, idx, V: int, scale: float = 1.0):
+    """dtable[v] = scale * sum over the rows r with idx[r] == v of dy[r]."""
+    dy = _f64(dy)
+    dt = np.zeros((V, dy.shape[1]), F64)
+    np.add.at(dt, np.asarray(idx, np.int64), scale * dy)
+    return dt
+
+
+def softmax_rows(s, scale: float = 1.0, causal: bool = False):
+    """Row softmax of scale * s over the last axis; with ``causal`` entry [i, j] takes part only for j <= i."""
+    z = scale * _f64(s)
+    if causal:
+        i, j = np.arange(z.shape[-2])[:, None], np.arange(z.shape[-1])[None, :]
+        z = np.where(j <= i, z, -np.inf)
+    z = z - z.max(axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def softmax_rows_bwd(p, dp, scale: float = 1.0):
+    """ds = scale * p * (dp - sum_j dp p)   (masked entries have p = 0, hence ds = 0)."""
+    p, dp = _f64(p), _f64(dp)
+    return scale * p * (dp - (dp * p).sum(axis=-1, keepdims=True))
+
+
+def attention_fwd(qkv, heads: int, causal: bool = False, store=None):
+    """qkv:[N,S,3E] = [q | k | v] per token; head h owns columns h*d .. (h+1)*d of each block, d = E/heads.
+    scores = q_h k_h^T, p = softmax(scores / sqrt(d)), ctx_h = p v_h.  ``store`` rounds the tensors
+    the device keeps between the three steps (scores, p).  Returns (ctx[N,S,E], p[N,heads,S,S])."""
+    st = store if store is not None else (lambda a: a)
+    qkv = _f64(qkv)
+    N, S, E3 = qkv.shape
+    E = E3 // 3
+    d = E // heads
+    sp = lambda a: a.reshape(N, S, heads, d).transpose(0, 2, 1, 3)          # [N,H,S,d]
+    q, k, v = sp(qkv[..., :E]), sp(qkv[..., E:2 * E]), sp(qkv[..., 2 * E:])
+    scores = st(q @ k.transpose(0, 1, 3, 2))
+    p = st(softmax_rows(scores, 1.0 / np.sqrt(d), causal))
+    ctx = (p @ v).transpose(0, 2, 1, 3).reshape(N, S, E)
+    return ctx, p
+
+
+def attention_bwd(qkv, p, dctx, heads: int, store=None):
+    """Backward of attention_fwd from the stored probabilities.  Returns dqkv[N,S,3E]."""
+    st = store if store is not None else (lambda a: a)
+    qkv, p, dctx = _f64(qkv), _f64(p), _f64(dctx)
+    N, S, E3 = qkv.shape
+    E = E3 // 3
+    d = E // heads
+    sp = lambda a: a.reshape(N, S, heads, d).transpose(0, 2, 1, 3)
+    un = lambda a: a.transpose(0, 2, 1, 3).reshape(N, S, E)
+    q, k, v, dc = sp(qkv[..., :E]), sp(qkv[..., E:2 * E]), sp(qkv[..., 2 * E:]), sp(dctx)
+    dv = p.transpose(0, 1, 3, 2) @ dc
+    dp = st(dc @ v.transpose(0, 1, 3, 2))
+    ds = st(softmax_rows_bwd(p, dp, 1.0 / np.sqrt(d)))
+    dq = ds @ k
+    dk = ds.transpose(0, 1, 3, 2) @ q
+    return np.concatenate([un(dq), un(dk), un(dv)], axis=2)
