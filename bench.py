@@ -38,6 +38,7 @@ class Tracer:
                      "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd",
                      "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_fwd",
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
+                     "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
                      "conv1x1_bn_maxpool_bwd")
 
     def __init__(self, hb, torch):
@@ -108,6 +109,12 @@ def kernel_label(name, a):
         return "colsum_kernel"
     if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
+    if name in ("attention_fwd", "attention_bwd"):
+        return name + ": batched head GEMMs + softmax_rows kernel"
+    if name in ("embedding_fwd", "embedding_bwd", "softmax_xent"):
+        return name + "_kernel"
+    if name == "softmax_xent_rows":
+        return "xent_rows_kernel"
     if name in ("add_sample_bias", "add_strided"):
         return "row_add_kernel"
     if name == "sum_points":
@@ -152,6 +159,9 @@ def algorithmic_flops(name, a):
     if name in ("conv1x1_fwd", "conv1x1_bwd"):
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * Co * L
+    if name in ("attention_fwd", "attention_bwd"):      # 2 (forward) / 4 (backward) products of S x S x d per head
+        B, N, S, E, H = a[:5]
+        return (2 if name == "attention_fwd" else 4) * 2.0 * B * N * S * S * E
     if name == "conv1x1_bn_maxpool_fwd":      # the Ci -> Co product (its output is reduced, never stored) + the Gram matrix
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * (Co + Ci) * L
@@ -212,6 +222,17 @@ def algorithmic_bytes(name, a):
             return act_bytes + wbytes * 4          # dW is fp32
         return act_bytes + wbytes * _es(dt)
     if name == "bias_act_nchw":
+        return 2 * a[0] * a[1] * a[2] * _es(a[3])
+    if name == "attention_fwd":               # qkv in, probabilities and context out
+        B, N, S, E, H, dt = a[:6]
+        return B * N * S * (4 * E + H * S) * _es(dt)
+    if name == "attention_bwd":               # qkv, probabilities, dctx in, dqkv out
+        B, N, S, E, H, dt = a[:6]
+        return B * N * S * (7 * E + H * S) * _es(dt)
+    if name in ("embedding_fwd", "embedding_bwd"):
+        B, R, V, E, dt = a[:5]
+        return B * R * E * 2 * _es(dt) if name == "embedding_fwd" else B * (R * E * _es(dt) + V * E * 4)
+    if name in ("softmax_xent", "softmax_xent_rows"):
         return 2 * a[0] * a[1] * a[2] * _es(a[3])
     if name in ("add_sample_bias", "softmax_xent_points"):
         return 2 * a[0] * a[1] * a[2] * a[3] * _es(a[4])
@@ -345,6 +366,15 @@ class Workload:
             self.config = {"workload": self.spec.name, "B": self.spec.B, "batch_per_model": self.spec.Nb,
                            "points": self.spec.L, "conv": list(self.spec.conv), "head": list(self.spec.head),
                            "step": "fwd+bwd+Adam"}
+        elif name == "t0":
+            from oracle import transformer as oracle_model
+            self.spec = hi.spec_t0()
+            self.inp = hi.transformer_inputs(self.spec)
+            self.cls = arrays.FusedTransformerLM
+            self.per_model_keys = ("tokens", "targets")
+            self.config = {"workload": self.spec.name, "B": self.spec.B, "sequences_per_model": self.spec.N,
+                           "tokens_per_sequence": self.spec.S, "width": self.spec.E, "heads": self.spec.heads,
+                           "ffn": self.spec.F, "layers": self.spec.layers, "vocab": self.spec.V, "step": "fwd+bwd+Adam"}
         elif name == "c3":
             from oracle import dcgan as oracle_model
             self.spec = hi.spec_c3()
@@ -399,6 +429,11 @@ class Workload:
             inp = hi.pointnet_seg_inputs(small)
             nsamp = small.Nb
             what = f"1 model x {small.Nb} clouds x {small.L} points"
+        elif self.name == "t0":
+            small = dataclasses.replace(self.spec, B=1, N=8)
+            inp = hi.transformer_inputs(small)
+            nsamp = small.N
+            what = f"1 model x {small.N} sequences x {small.S} tokens, {small.layers} layers, vocabulary {small.V}"
         elif self.name == "c3":
             small = dataclasses.replace(self.spec, B=1, Nb=4)
             inp = hi.dcgan_inputs(small)
@@ -434,7 +469,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4", "t0"])
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--ops-report", default=None,

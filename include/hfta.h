@@ -311,6 +311,40 @@ int hfta_adam_step_multi(int B, int nseg, const int64_t* seg_offsets, int grad_d
                          const float* weight_decay, int step_t, int decoupled_wd, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Fused Embedding and the core of fused multi-head attention (fusion rules table rows "Embedding":
+ * one table of B*V rows with the indices of model b offset by b*V, here table [B][V][E] and indices
+ * [B][R]; and "MultiheadAttention", which the table builds from the Linear rule: the input and
+ * output projections are hfta_linear_fwd/bwd, the rest is per (model, sequence, head)).
+ *   embedding_fwd: out[b,r,:] = scale * table[b, idx[b,r], :] (+ pos[r % S, :], fp32 [S][E], or NULL);
+ *                  storage dtype; indices clamped to [0, V).
+ *   embedding_bwd: dtable[b,v,:] (fp32, fully written) = scale * sum over r with idx[b,r] == v of dY[b,r,:],
+ *                  added in order of r (bit-reproducible); R*8 bytes of LDS per workgroup: EUNSUPPORTED
+ *                  above 7680 rows per model.
+ *   attention_fwd: QKV [B][N][S][3E] = [q | k | v] per token, head h owns columns h*d..(h+1)*d of each
+ *                  block (d = E/H).  P [B][N][H][S][S] (storage dtype) receives softmax(q k^T / sqrt(d))
+ *                  (with causal != 0 entry [i][j] takes part only for j <= i, the rest is 0); CTX
+ *                  [B][N][S][E] = P v, heads side by side.  No head split or transpose is materialised.
+ *   attention_bwd: dQKV (same layout as QKV, fully written) from QKV, the saved P and dCTX; workspace
+ *                  of hfta_attention_bwd_workspace_bytes (one score-sized buffer), else EWORKSPACE.
+ * B*N*H <= 65535 (EUNSUPPORTED above); E must be a multiple of H (EINVAL).
+ * ---------------------------------------------------------------------- */
+/* hfta_softmax_xent for wide class axes (a vocabulary): one workgroup per row instead of one thread;
+ * same results up to fp32 summation order; row terms pass through the workspace
+ * (hfta_softmax_xent_rows_workspace_bytes, else EWORKSPACE) and are added per model in a fixed order. */
+size_t hfta_softmax_xent_rows_workspace_bytes(int B, int R);
+int hfta_softmax_xent_rows(int B, int R, int K, int dtype, const void* logits, const int32_t* labels,
+                           float* loss, void* dlogits, void* workspace, size_t ws_bytes, void* stream);
+int hfta_embedding_fwd(int B, int R, int V, int E, int dtype, const void* table, const int32_t* idx,
+                       float scale, const float* pos, int S, void* out, void* stream);
+int hfta_embedding_bwd(int B, int R, int V, int E, int dtype, const void* dY, const int32_t* idx,
+                       float scale, float* dtable, void* stream);
+int hfta_attention_fwd(int B, int N, int S, int E, int H, int dtype, const void* QKV, void* P, void* CTX,
+                       int causal, void* stream);
+size_t hfta_attention_bwd_workspace_bytes(int B, int N, int S, int E, int H, int dtype);
+int hfta_attention_bwd(int B, int N, int S, int E, int H, int dtype, const void* QKV, const void* P,
+                       const void* dCTX, void* dQKV, void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Fused Adadelta over the same parameter-major arena, and the fused step learning-rate schedule
  * (section "Our Proposal: HFTA", paragraph on optimizers and learning-rate schedulers: each
  * hyper-parameter becomes a vector with one entry per model).  Arguments as hfta_adam_step_multi;

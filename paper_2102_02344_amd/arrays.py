@@ -864,3 +864,129 @@ class FusedPointNetSeg(ParamArena):
             P("conv1x1_bwd", layer=k, x=xinv, w=self.w(k + ".w"), dy=dz.view(Nb, B * co, L),
               dx=None if i == 0 else dnext.view(Nb, B * ci, L), dw=self.g(k + ".w"), db=self.g(k + ".b"))
         return self.loss
+
+
+class FusedTransformerLM(ParamArena):
+    """Transformer-encoder language-model array: fused Embedding (scaled, plus fixed positions), post-norm
+    encoder layers with causal multi-head attention (projections are fused Linears, the per-head
+    products run as batched GEMMs on column blocks of the packed projection), Linear decoder, softmax
+    cross-entropy per token, Adam.  Activations are ``[B, R, F]`` with R = N*S tokens per model."""
+
+    LN_EPS = 1e-5
+
+    def __init__(self, spec, inp: dict, device: str = "cuda"):
+        import hfta_inputs as hi
+        from math import sqrt
+        self.spec = spec
+        self.B, self.N, self.S, self.E, self.F, self.V, self.Hh = spec.B, spec.N, spec.S, spec.E, spec.F, spec.V, spec.heads
+        self.R = spec.N * spec.S
+        self.dtype, self.dt, self.tdt = spec.dtype, _DT[spec.dtype], _TDT[spec.dtype]
+        self.dev = torch.device(device)
+        B, R, E, F, V, N, S, Hh = self.B, self.R, self.E, self.F, self.V, self.N, self.S, self.Hh
+        self._init_arena(hi.transformer_param_shapes(spec), B, inp, spec.dtype, self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        act = dict(dtype=self.tdt, device=self.dev)
+        nl = spec.layers
+        self.scale = sqrt(E)
+        self.tokens = torch.from_numpy(inp["tokens"].reshape(B, R)).to(self.dev)
+        self.targets = torch.from_numpy(inp["targets"].reshape(B, R)).to(self.dev)
+        # the fixed position table, float32 (computed on the host in float64 by its closed form)
+        pos = torch.arange(S, dtype=torch.float64)[:, None]
+        div = torch.exp(torch.arange(0, E, 2, dtype=torch.float64) * (-np.log(10000.0) / E))
+        pe = torch.zeros(S, E, dtype=torch.float64)
+        pe[:, 0::2] = torch.sin(pos * div)
+        pe[:, 1::2] = torch.cos(pos * div)[:, :E // 2]
+        self.pos = pe.to(torch.float32).to(self.dev)
+        self.x = [torch.empty(B, R, E, **act) for _ in range(nl + 1)]
+        self.qkv = [torch.empty(B, R, 3 * E, **act) for _ in range(nl)]
+        self.p = [torch.empty(B, N, Hh, S, S, **act) for _ in range(nl)]
+        self.ctx = [torch.empty(B, R, E, **act) for _ in range(nl)]
+        self.s1 = [torch.empty(B, R, E, **act) for _ in range(nl)]
+        self.x1 = [torch.empty(B, R, E, **act) for _ in range(nl)]
+        self.h = [torch.empty(B, R, F, **act) for _ in range(nl)]
+        self.s2 = [torch.empty(B, R, E, **act) for _ in range(nl)]
+        self.tmpE = torch.empty(B, R, E, **act)
+        self.stats = [[torch.empty(B * R, **f32) for _ in range(4)] for _ in range(nl)]   # mean1, invstd1, mean2, invstd2
+        self.logits = torch.empty(B, R, V, **act)
+        self.dlogits = torch.empty(B, R, V, **act)
+        self.dE = [torch.empty(B, R, E, **act) for _ in range(4)]
+        self.dF = [torch.empty(B, R, F, **act) for _ in range(2)]
+        self.dqkv = torch.empty(B, R, 3 * E, **act)
+        self.loss = torch.empty(B, **f32)
+        ws = max(4, hb.layernorm_bwd_workspace_bytes(B, R, E), hb.attention_bwd_workspace_bytes(B, N, S, E, Hh, self.dt),
+                 hb.softmax_xent_rows_workspace_bytes(B, R),
+                 hb.linear_bwd_workspace_bytes(B, R, E, 3 * E, self.dt), hb.linear_bwd_workspace_bytes(B, R, E, F, self.dt),
+                 hb.linear_bwd_workspace_bytes(B, R, F, E, self.dt), hb.linear_bwd_workspace_bytes(B, R, E, V, self.dt))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+
+    def _lin_bwd(self, P, name, M, Fx, Fy, x, dy, dx):
+        hb.linear_bwd(self.B, M, Fx, Fy, self.dt, x, self.w(name + ".w"), dy, dx, self.g(name + ".w"), self.g(name + ".b"), self.ws)
+        P("linear_bwd", layer=name, x=x, w=self.w(name + ".w"), dy=dy, dx=dx, dw=self.g(name + ".w"), db=self.g(name + ".b"))
+
+    def forward_backward(self, probe=None):
+        B, R, E, F, V, N, S, Hh, dt = self.B, self.R, self.E, self.F, self.V, self.N, self.S, self.Hh, self.dt
+        P = probe if probe is not None else (lambda op, **kw: None)
+        nl = self.spec.layers
+        hb.embedding_fwd(B, R, V, E, dt, self.w("emb"), self.tokens, self.scale, self.pos, S, self.x[0])
+        P("embedding_fwd", table=self.w("emb"), idx=self.tokens, pos=self.pos, y=self.x[0])
+        for i in range(nl):
+            k, x = f"l{i}", self.x[i]
+            mu1, inv1, mu2, inv2 = self.stats[i]
+            hb.linear_fwd(B, R, E, 3 * E, dt, x, self.w(k + ".in.w"), self.w(k + ".in.b"), self.qkv[i])
+            P("linear_fwd", layer=k + ".in", x=x, w=self.w(k + ".in.w"), b=self.w(k + ".in.b"), y=self.qkv[i], act=0)
+            hb.attention_fwd(B, N, S, E, Hh, dt, self.qkv[i], self.p[i], self.ctx[i], 1)
+            P("attention_fwd", qkv=self.qkv[i], p=self.p[i], ctx=self.ctx[i])
+            hb.linear_fwd(B, R, E, E, dt, self.ctx[i], self.w(k + ".out.w"), self.w(k + ".out.b"), self.tmpE)
+            P("linear_fwd", layer=k + ".out", x=self.ctx[i], w=self.w(k + ".out.w"), b=self.w(k + ".out.b"), y=self.tmpE, act=0)
+            hb.add(B * R * E, dt, x, self.tmpE, self.s1[i])
+            P("add", a=x, b=self.tmpE, y=self.s1[i])
+            hb.layernorm_fwd(B, R, E, dt, self.s1[i], self.master(k + ".ln1.w"), self.master(k + ".ln1.b"), self.LN_EPS,
+                             mu1, inv1, self.x1[i])
+            P("layernorm_fwd", layer=k + ".ln1", x=self.s1[i], w=self.master(k + ".ln1.w"), b=self.master(k + ".ln1.b"),
+              y=self.x1[i], mean=mu1, invstd=inv1)
+            hb.linear_fwd(B, R, E, F, dt, self.x1[i], self.w(k + ".ff1.w"), self.w(k + ".ff1.b"), self.h[i], hb.ACT_RELU)
+            P("linear_fwd", layer=k + ".ff1", x=self.x1[i], w=self.w(k + ".ff1.w"), b=self.w(k + ".ff1.b"), y=self.h[i], act=1)
+            hb.linear_fwd(B, R, F, E, dt, self.h[i], self.w(k + ".ff2.w"), self.w(k + ".ff2.b"), self.tmpE)
+            P("linear_fwd", layer=k + ".ff2", x=self.h[i], w=self.w(k + ".ff2.w"), b=self.w(k + ".ff2.b"), y=self.tmpE, act=0)
+            hb.add(B * R * E, dt, self.x1[i], self.tmpE, self.s2[i])
+            P("add", a=self.x1[i], b=self.tmpE, y=self.s2[i])
+            hb.layernorm_fwd(B, R, E, dt, self.s2[i], self.master(k + ".ln2.w"), self.master(k + ".ln2.b"), self.LN_EPS,
+                             mu2, inv2, self.x[i + 1])
+            P("layernorm_fwd", layer=k + ".ln2", x=self.s2[i], w=self.master(k + ".ln2.w"), b=self.master(k + ".ln2.b"),
+              y=self.x[i + 1], mean=mu2, invstd=inv2)
+        hb.linear_fwd(B, R, E, V, dt, self.x[nl], self.w("dec.w"), self.w("dec.b"), self.logits)
+        P("linear_fwd", layer="dec", x=self.x[nl], w=self.w("dec.w"), b=self.w("dec.b"), y=self.logits, act=0)
+        hb.softmax_xent_rows(B, R, V, dt, self.logits, self.targets, self.loss, self.dlogits, self.ws)
+        P("softmax_xent", logits=self.logits, labels=self.targets, loss=self.loss, d=self.dlogits)
+        # ---- backward
+        d = self.dE[0]
+        self._lin_bwd(P, "dec", R, E, V, self.x[nl], self.dlogits, d)
+        for i in reversed(range(nl)):
+            k = f"l{i}"
+            mu1, inv1, mu2, inv2 = self.stats[i]
+            ds2, t1, t2 = self.dE[1], self.dE[2], self.dE[3]
+            hb.layernorm_bwd(B, R, E, dt, self.s2[i], d, self.master(k + ".ln2.w"), mu2, inv2, ds2,
+                             self.g(k + ".ln2.w"), self.g(k + ".ln2.b"), self.ws)
+            P("layernorm_bwd", layer=k + ".ln2", x=self.s2[i], dy=d, w=self.master(k + ".ln2.w"), mean=mu2, invstd=inv2,
+              dx=ds2, dw=self.g(k + ".ln2.w"), db=self.g(k + ".ln2.b"))
+            self._lin_bwd(P, k + ".ff2", R, F, E, self.h[i], ds2, self.dF[0])
+            hb.act_bwd(B * R * F, dt, self.h[i], self.dF[0], self.dF[1], hb.ACT_RELU, 0.0, 1)
+            P("relu_bwd_from_output", y=self.h[i], dy=self.dF[0], dx=self.dF[1])
+            self._lin_bwd(P, k + ".ff1", R, E, F, self.x1[i], self.dF[1], t1)
+            hb.add(B * R * E, dt, ds2, t1, t2)
+            P("add", a=ds2, b=t1, y=t2)
+            ds1 = self.dE[1]                                   # ds2 is consumed
+            hb.layernorm_bwd(B, R, E, dt, self.s1[i], t2, self.master(k + ".ln1.w"), mu1, inv1, ds1,
+                             self.g(k + ".ln1.w"), self.g(k + ".ln1.b"), self.ws)
+            P("layernorm_bwd", layer=k + ".ln1", x=self.s1[i], dy=t2, w=self.master(k + ".ln1.w"), mean=mu1, invstd=inv1,
+              dx=ds1, dw=self.g(k + ".ln1.w"), db=self.g(k + ".ln1.b"))
+            self._lin_bwd(P, k + ".out", R, E, E, self.ctx[i], ds1, t1)            # t1 = dctx
+            hb.attention_bwd(B, N, S, E, Hh, dt, self.qkv[i], self.p[i], t1, self.dqkv, self.ws)
+            P("attention_bwd", qkv=self.qkv[i], p=self.p[i], dctx=t1, dqkv=self.dqkv)
+            self._lin_bwd(P, k + ".in", R, E, 3 * E, self.x[i], self.dqkv, t2)
+            hb.add(B * R * E, dt, ds1, t2, self.dE[0])
+            P("add", a=ds1, b=t2, y=self.dE[0])
+            d = self.dE[0]
+        hb.embedding_bwd(B, R, V, E, dt, d, self.tokens, self.scale, self.g("emb"))
+        P("embedding_bwd", dy=d, idx=self.tokens, dtable=self.g("emb"))
+        return self.loss

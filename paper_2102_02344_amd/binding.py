@@ -58,6 +58,13 @@ _SIGS = {
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
     "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 21 + [_i, _f, _p, _sz, _p]),
+    "hfta_softmax_xent_rows_workspace_bytes": (_sz, [_i, _i]),
+    "hfta_softmax_xent_rows": (_i, [_i] * 4 + [_p] * 5 + [_sz, _p]),
+    "hfta_embedding_fwd": (_i, [_i] * 5 + [_p, _p, _f, _p, _i, _p, _p]),
+    "hfta_embedding_bwd": (_i, [_i] * 5 + [_p, _p, _f, _p, _p]),
+    "hfta_attention_fwd": (_i, [_i] * 6 + [_p, _p, _p, _i, _p]),
+    "hfta_attention_bwd_workspace_bytes": (_sz, [_i] * 6),
+    "hfta_attention_bwd": (_i, [_i] * 6 + [_p, _p, _p, _p, _p, _sz, _p]),
     "hfta_adadelta_step_multi": (_i, [_i, _i, _s4, _i] + [_p] * 9 + [_p]),
     "hfta_steplr": (_i, [_i, _p, _p, _p, _i, _p, _p]),
     "hfta_add_sample_bias": (_i, [_i] * 5 + [_p] * 7),
@@ -390,3 +397,38 @@ def adadelta_step_multi(B, seg_offsets, grad_dtype, theta, grad, square_avg, acc
 def steplr(B, base_lr, gamma, step_size, epoch, lr, stream=None):
     _check(_lib.hfta_steplr(B, _ptr(base_lr), _ptr(gamma), _ptr(step_size), epoch, _ptr(lr), _stream(stream)),
            "hfta_steplr")
+
+
+def embedding_fwd(B, R, V, E, dtype, table, idx, scale, pos, S, out, stream=None):
+    _check(_lib.hfta_embedding_fwd(B, R, V, E, dtype, _ptr(table), _ptr(idx), scale, _ptr(pos), S, _ptr(out),
+                                   _stream(stream)), "hfta_embedding_fwd")
+
+
+def embedding_bwd(B, R, V, E, dtype, dY, idx, scale, dtable, stream=None):
+    _check(_lib.hfta_embedding_bwd(B, R, V, E, dtype, _ptr(dY), _ptr(idx), scale, _ptr(dtable), _stream(stream)),
+           "hfta_embedding_bwd")
+
+
+def attention_fwd(B, N, S, E, H, dtype, QKV, P, CTX, causal=0, stream=None):
+    _check(_lib.hfta_attention_fwd(B, N, S, E, H, dtype, _ptr(QKV), _ptr(P), _ptr(CTX), causal, _stream(stream)),
+           "hfta_attention_fwd")
+
+
+def attention_bwd_workspace_bytes(B, N, S, E, H, dtype):
+    return _lib.hfta_attention_bwd_workspace_bytes(B, N, S, E, H, dtype)
+
+
+def attention_bwd(B, N, S, E, H, dtype, QKV, P, dCTX, dQKV, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_attention_bwd(B, N, S, E, H, dtype, _ptr(QKV), _ptr(P), _ptr(dCTX), _ptr(dQKV), wp, wb,
+                                   _stream(stream)), "hfta_attention_bwd")
+
+
+def softmax_xent_rows_workspace_bytes(B, R):
+    return _lib.hfta_softmax_xent_rows_workspace_bytes(B, R)
+
+
+def softmax_xent_rows(B, R, K, dtype, logits, labels, loss, dlogits, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_softmax_xent_rows(B, R, K, dtype, _ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits), wp, wb,
+                                       _stream(stream)), "hfta_softmax_xent_rows")

@@ -397,3 +397,38 @@ def test_c2_full_size_step_sampled():
     assert set(seen) == {"conv1x1_fwdconv4", "conv1x1_fwdhead0", "conv1x1_fwdhead3", "add_sample_bias", "softmax_xent_points",
                          "sum_points", "add_strided", "maxpool_points_bwd_add", "conv1x1_bwdhead0", "conv1x1_bwdconv4"}
     assert np.all(np.isfinite(arr.loss.cpu().numpy()))
+
+
+def test_t0_attention_full_size_sampled():
+    """The attention core at the Transformer workload's size (B=8, 32 sequences of 64 tokens, width
+    256, 4 heads, bf16, causal): sampled probabilities, context and gradient entries recomputed by
+    their definitions from the bits the GPU read and stored."""
+    from paper_2102_02344_amd import binding as hb
+    B, N, S, E, H = 8, 32, 64, 256, 4
+    d = E // H
+    g = torch.Generator(device="cuda").manual_seed(61)
+    QKV = torch.randn(B, N, S, 3 * E, device="cuda", generator=g).to(bf)
+    dCTX = torch.randn(B, N, S, E, device="cuda", generator=g).to(bf)
+    P = torch.empty(B, N, H, S, S, device="cuda", dtype=bf)
+    CTX = torch.empty(B, N, S, E, device="cuda", dtype=bf)
+    dQKV = torch.empty_like(QKV)
+    ws = torch.empty(hb.attention_bwd_workspace_bytes(B, N, S, E, H, DT["bf16"]), dtype=torch.uint8, device="cuda")
+    hb.attention_fwd(B, N, S, E, H, DT["bf16"], QKV, P, CTX, 1)
+    hb.attention_bwd(B, N, S, E, H, DT["bf16"], QKV, P, dCTX, dQKV, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(62)
+    K_ = 400
+    for b, n, h in zip(*(rng.integers(0, m, 6) for m in (B, N, H))):
+        q, k, v = (f64(QKV[b, n, :, j * E + h * d:j * E + (h + 1) * d]) for j in range(3))
+        sc = oops.store(q @ k.T, "bf16")
+        p = oops.softmax_rows(sc, 1.0 / np.sqrt(d), True)
+        gp = f64(P[b, n, h])
+        rel_ok(gp, oops.store(p, "bf16"), TOL["bf16"], "P")
+        assert np.all(np.triu(gp, 1) == 0.0)
+        rel_ok(f64(CTX[b, n, :, h * d:(h + 1) * d]), gp @ v, TOL["bf16"], "ctx")          # from the stored probabilities
+        dc = f64(dCTX[b, n, :, h * d:(h + 1) * d])
+        dp = oops.store(dc @ v.T, "bf16")
+        ds = oops.store(oops.softmax_rows_bwd(gp, dp, 1.0 / np.sqrt(d)), "bf16")
+        rel_ok(f64(dQKV[b, n, :, h * d:(h + 1) * d]), ds @ k, TOL["bf16"], "dq")
+        rel_ok(f64(dQKV[b, n, :, E + h * d:E + (h + 1) * d]), ds.T @ q, TOL["bf16"], "dk")
+        rel_ok(f64(dQKV[b, n, :, 2 * E + h * d:2 * E + (h + 1) * d]), gp.T @ dc, TOL["bf16"], "dv")
