@@ -470,6 +470,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4", "t0"])
+    ap.add_argument("--unfused", type=int, default=0,
+                    help="config 1 only: run the first K per-point layers (and their share of Adam) model by model "
+                         "(partial fusion); the headline line is K = 0")
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--ops-report", default=None,
@@ -500,7 +503,9 @@ def main():
 
     tracer = Tracer(binding, torch)
     arrays.hb = tracer
-    arr = wl.cls(spec, inp)
+    arr = wl.cls(spec, inp, unfused_layers=tuple(range(args.unfused))) if (args.unfused and args.workload == "c1") else wl.cls(spec, inp)
+    if args.unfused and args.workload == "c1":
+        wl.config["unfused_per_point_layers"] = args.unfused
     # Warm-up.  Its last steps bracket EVERY traced entry point with HIP events: the per-kernel table,
     # and which entry has the largest share of a step.  (Two events per call cost host time, about
     # as much as a whole step of this workload for ~50 calls, so the timed region cannot carry them all.)

@@ -100,6 +100,36 @@ class ParamArena:
         hb.adam_step_multi(self.B, self.seg_offsets, hb.F32, self.theta, self.grad, self.m, self.v, self.lowp,
                            self.hp["lr"], self.hp["beta1"], self.hp["beta2"], self.hp["eps"], self.hp["wd"], self.t)
 
+    def adam_partial(self, unfused_prefixes):
+        """Partially fused optimiser (section "Results", partial-fusion study): parameters whose name
+        starts with one of ``unfused_prefixes`` are stepped model by model (B launches of the
+        single-arena kernel each), the contiguous runs of all other parameters stay fused."""
+        self.t += 1
+        B, off, names = self.B, self.seg_offsets, [n for n, _ in self.shapes]
+        unf = [any(n.startswith(p) for p in unfused_prefixes) for n in names]
+        lp = self.lowp
+        hp = self.hp
+        j = 0
+        while j < len(names):
+            if unf[j]:
+                n = off[j + 1] - off[j]
+                for b in range(B):
+                    o = B * off[j] + b * n
+                    hb.adam_step(1, n, hb.F32, self.theta[o:], self.grad[o:], self.m[o:], self.v[o:],
+                                 None if lp is None else lp[o:], hp["lr"][b:], hp["beta1"][b:], hp["beta2"][b:],
+                                 hp["eps"][b:], hp["wd"][b:], self.t)
+                j += 1
+                continue
+            j1 = j
+            while j1 < len(names) and not unf[j1]:
+                j1 += 1
+            o = B * off[j]
+            rel = [off[q] - off[j] for q in range(j, j1 + 1)]
+            hb.adam_step_multi(B, rel, hb.F32, self.theta[o:], self.grad[o:], self.m[o:], self.v[o:],
+                               None if lp is None else lp[o:], hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["wd"],
+                               self.t)
+            j = j1
+
     def adadelta(self, rho: torch.Tensor, eps: torch.Tensor):
         """Adadelta instead of Adam (``rho``, ``eps``: device ``[B]``); the two state buffers hold
         the running square average and the accumulated squared delta."""
@@ -121,11 +151,24 @@ class FusedPointNetCls(ParamArena):
     """PointNet-classification-style array (per-point k=1 convolutions + BatchNorm +
     ReLU, max over points, fully connected head, softmax cross-entropy, Adam)."""
 
+    def train_step(self):
+        loss = self.forward_backward()
+        if self.unfused:
+            self.adam_partial([f"conv{i}." for i in self.unfused])
+        else:
+            self.adam()
+        return loss
+
     BN_EPS = 1e-5
     BN_MOMENTUM = 0.1
 
-    def __init__(self, spec, inp: dict, device: str = "cuda", fused_tail: bool = True):
+    def __init__(self, spec, inp: dict, device: str = "cuda", fused_tail: bool = True, unfused_layers=()):
+        """``unfused_layers``: indices of per-point layers (convolution + BatchNorm, forward and
+        backward, and their share of the optimiser) that run model by model -- B launches with B = 1
+        on the same buffers -- instead of once for the whole array: the partial fusion of the
+        paper's sensitivity study.  The last per-point layer stays fused when ``fused_tail`` applies."""
         self.spec = spec
+        self.unfused = frozenset(int(i) for i in unfused_layers)
         self.B, self.Nb, self.L = spec.B, spec.Nb, spec.L
         self.dtype = spec.dtype
         self.dt = _DT[spec.dtype]
@@ -220,6 +263,10 @@ class FusedPointNetCls(ParamArena):
                   mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"], zhit=self.zhit)
                 ci = co
                 break
+            if i in self.unfused and i < self.nconv - 1:
+                self._layer_fwd_unfused(i, x, ci, co)
+                x, ci = self.a[i], co
+                continue
             hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
                            self.z[i], _cs(B, co, L))
             P("conv1x1_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
@@ -344,6 +391,12 @@ class FusedPointNetCls(ParamArena):
                 da = dxin
                 continue
             dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
+            if i in self.unfused and i < self.nconv - 1:
+                xin = self.points if i == 0 else self.a[i - 1]
+                dxin = None if i == 0 else self.dbuf[cur][:Nb * B * ci * L]
+                self._layer_bwd_unfused(i, xin, ci, co, da, dz, dxin)
+                da = dxin
+                continue
             if i == self.nconv - 1:
                 hb.bn_bwd_maxpool(B, Nb, co, L, dt, self.z[i], cs, dpool, self.pool_idx, (Nb * co, co, 1),
                                   self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],
@@ -375,6 +428,46 @@ class FusedPointNetCls(ParamArena):
             da = dxin
         return self.loss
 
+
+
+
+def _unfused_methods():
+    def _off(t, n):
+        return t.view(-1)[n:]
+
+    def _layer_fwd_unfused(self, i, x, ci, co):
+        B, Nb, L, dt, k = self.B, self.Nb, self.L, self.dt, f"conv{i}"
+        xs, cs = _cs(B, ci, L), _cs(B, co, L)
+        for b in range(B):
+            hb.conv1x1_fwd(1, Nb, ci, co, L, dt, _off(x, b * ci * L), xs, _off(self.w(k + ".w"), b * co * ci),
+                           _off(self.w(k + ".b"), b * co), _off(self.z[i], b * co * L), cs)
+            hb.bn_fwd(1, Nb, co, L, dt, _off(self.z[i], b * co * L), cs, _off(self.master(k + ".bn.g"), b * co),
+                      _off(self.master(k + ".bn.b"), b * co), self.BN_EPS, self.BN_MOMENTUM,
+                      _off(self.running[k + ".bn.rm"], b * co), _off(self.running[k + ".bn.rv"], b * co),
+                      _off(self.saved[k + ".bn.mean"], b * co), _off(self.saved[k + ".bn.invstd"], b * co),
+                      _off(self.a[i], b * co * L), cs, hb.ACT_RELU)
+
+    def _layer_bwd_unfused(self, i, xin, ci, co, da, dz, dxin):
+        B, Nb, L, dt, k = self.B, self.Nb, self.L, self.dt, f"conv{i}"
+        xs, cs = _cs(B, ci, L), _cs(B, co, L)
+        for b in range(B):
+            hb.bn_bwd(1, Nb, co, L, dt, _off(self.z[i], b * co * L), cs, _off(da, b * co * L), cs,
+                      _off(self.master(k + ".bn.g"), b * co), _off(self.master(k + ".bn.b"), b * co),
+                      _off(self.saved[k + ".bn.mean"], b * co), _off(self.saved[k + ".bn.invstd"], b * co),
+                      _off(dz, b * co * L), cs, _off(self.g(k + ".bn.g"), b * co), _off(self.g(k + ".bn.b"), b * co),
+                      hb.ACT_RELU, 0.0, _off(self.g(k + ".b"), b * co))
+        for b in range(B):      # only now: dxin shares its buffer with da, which every model's BatchNorm has read
+            if dxin is not None:
+                hb.conv1x1_bwd(1, Nb, ci, co, L, dt, None, None, _off(self.w(k + ".w"), b * co * ci), _off(dz, b * co * L),
+                               cs, _off(dxin, b * ci * L), xs, None, None, self.ws)
+            hb.conv1x1_bwd(1, Nb, ci, co, L, dt, _off(xin, b * ci * L), xs, None, _off(dz, b * co * L), cs, None, None,
+                           _off(self.g(k + ".w"), b * co * ci), None, self.ws)
+
+    FusedPointNetCls._layer_fwd_unfused = _layer_fwd_unfused
+    FusedPointNetCls._layer_bwd_unfused = _layer_bwd_unfused
+
+
+_unfused_methods()
 
 
 class FusedMlp(ParamArena):
