@@ -328,6 +328,19 @@ int hfta_adam_step_multi(int B, int nseg, const int64_t* seg_offsets, int grad_d
  *                  of hfta_attention_bwd_workspace_bytes (one score-sized buffer), else EWORKSPACE.
  * B*N*H <= 65535 (EUNSUPPORTED above); E must be a multiple of H (EINVAL).
  * ---------------------------------------------------------------------- */
+/* Per-sample point transform of the point-cloud models (input / feature transform: a matrix
+ * predicted per cloud and applied to all its points; the Linear / Conv1d rule with the weight indexed
+ * by the sample as well as by the model).  X, Y, dY, dX: [b][n][c][l] with element strides (unit point
+ * stride); T, dT: [B][Nb][Co][Ci] contiguous, storage dtype (T is an activation of the transform
+ * sub-network, so its gradient is one too).
+ *   fwd: Y[b,n,o,l] = sum_c T[b,n,o,c] X[b,n,c,l]
+ *   bwd: dX[b,n,c,l] = sum_o T[b,n,o,c] dY[b,n,o,l] (NULL = skip);  dT[b,n,o,c] = sum_l dY[b,n,o,l] X[b,n,c,l] (NULL = skip)
+ * One batched GEMM over (model, sample) each.  B*Nb <= 65535 (EUNSUPPORTED above). */
+int hfta_point_transform_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                             const void* T, void* Y, const int64_t ys[4], void* stream);
+int hfta_point_transform_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                             const void* T, const void* dY, const int64_t dys[4], void* dX, const int64_t dxs[4],
+                             void* dT, void* stream);
 /* hfta_softmax_xent for wide class axes (a vocabulary): one workgroup per row instead of one thread;
  * same results up to fp32 summation order; row terms pass through the workspace
  * (hfta_softmax_xent_rows_workspace_bytes, else EWORKSPACE) and are added per model in a fixed order. */

@@ -546,3 +546,20 @@ def attention_bwd(qkv, p, dctx, heads: int, store=None):
     dq = ds @ k
     dk = ds.transpose(0, 1, 3, 2) @ q
     return np.concatenate([un(dq), un(dk), un(dv)], axis=2)
+
+
+# --------------------------------------------------------------------------
+# Per-sample point transform (the point-cloud models' input / feature transform:
+# a matrix predicted per cloud, applied to all its points; one batched product
+# per (model, sample), an instance of the Linear rule with the weight indexed by
+# the sample as well)
+# --------------------------------------------------------------------------
+def point_transform_fwd(x, t):
+    """x:[N,Ci,L], t:[N,Co,Ci] -> y[n,o,l] = sum_c t[n,o,c] x[n,c,l]."""
+    return np.einsum("noc,ncl->nol", _f64(t), _f64(x))
+
+
+def point_transform_bwd(x, t, dy):
+    """Returns (dx[n,c,l] = sum_o t[n,o,c] dy[n,o,l],  dt[n,o,c] = sum_l dy[n,o,l] x[n,c,l])."""
+    x, t, dy = _f64(x), _f64(t), _f64(dy)
+    return np.einsum("noc,nol->ncl", t, dy), np.einsum("nol,ncl->noc", dy, x)

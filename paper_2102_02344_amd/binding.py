@@ -58,6 +58,8 @@ _SIGS = {
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
     "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 21 + [_i, _f, _p, _sz, _p]),
+    "hfta_point_transform_fwd": (_i, [_i] * 6 + [_p] * 6),
+    "hfta_point_transform_bwd": (_i, [_i] * 6 + [_p] * 9),
     "hfta_softmax_xent_rows_workspace_bytes": (_sz, [_i, _i]),
     "hfta_softmax_xent_rows": (_i, [_i] * 4 + [_p] * 5 + [_sz, _p]),
     "hfta_embedding_fwd": (_i, [_i] * 5 + [_p, _p, _f, _p, _i, _p, _p]),
@@ -432,3 +434,14 @@ def softmax_xent_rows(B, R, K, dtype, logits, labels, loss, dlogits, workspace=N
     wp, wb = _ws(workspace)
     _check(_lib.hfta_softmax_xent_rows(B, R, K, dtype, _ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits), wp, wb,
                                        _stream(stream)), "hfta_softmax_xent_rows")
+
+
+def point_transform_fwd(B, Nb, Ci, Co, L, dtype, X, xs, T, Y, ys, stream=None):
+    _check(_lib.hfta_point_transform_fwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(T), _ptr(Y), _strides(ys),
+                                         _stream(stream)), "hfta_point_transform_fwd")
+
+
+def point_transform_bwd(B, Nb, Ci, Co, L, dtype, X, xs, T, dY, dys, dX, dxs, dT, stream=None):
+    _check(_lib.hfta_point_transform_bwd(B, Nb, Ci, Co, L, dtype, _ptr(X), None if xs is None else _strides(xs), _ptr(T),
+                                         _ptr(dY), _strides(dys), _ptr(dX), None if dxs is None else _strides(dxs),
+                                         _ptr(dT), _stream(stream)), "hfta_point_transform_bwd")

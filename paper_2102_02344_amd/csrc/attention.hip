@@ -332,4 +332,48 @@ int hfta_softmax_xent_rows(int B, int R, int K, int dtype, const void* logits, c
   return launch_status();
 }
 
+// Per-sample point transform (the point-cloud models' input / feature transform): the weight of this
+// k=1 convolution is indexed by the sample as well as by the model, T:[B][Nb][Co][Ci].
+int hfta_point_transform_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                             const void* T, void* Y, const int64_t ys[4], void* stream) {
+  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !T || !Y || !ys) return HFTA_EINVAL;
+  if (xs[3] != 1 || ys[3] != 1 || (int64_t)B * Nb > 65535) return HFTA_EUNSUPPORTED;
+  GemmDesc g = head_desc(B, 1, Nb, dtype);
+  g.A = T; g.Bm = X; g.C = Y;
+  g.M = Co; g.N = L; g.K = Ci;
+  g.a_kc = true; g.a_ld = Ci; g.a_g0 = (int64_t)Nb * Co * Ci; g.a_g1 = (int64_t)Co * Ci;
+  g.b_kc = false; g.b_ld = xs[2]; g.b_g0 = xs[0]; g.b_g1 = xs[1];
+  g.c_ld = ys[2]; g.c_g0 = ys[0]; g.c_g1 = ys[1];
+  return gemm_launch(g, as_stream(stream));
+}
+
+int hfta_point_transform_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                             const void* T, const void* dY, const int64_t dys[4], void* dX, const int64_t dxs[4],
+                             void* dT, void* stream) {
+  if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !dY || !dys) return HFTA_EINVAL;
+  if ((dX && (!T || !dxs)) || (dT && (!X || !xs))) return HFTA_EINVAL;
+  if (dys[3] != 1 || (dX && dxs[3] != 1) || (dT && xs[3] != 1) || (int64_t)B * Nb > 65535) return HFTA_EUNSUPPORTED;
+  hipStream_t st = as_stream(stream);
+  if (dX) {      // dX[c][l] = sum_o T[o][c] dY[o][l]
+    GemmDesc g = head_desc(B, 1, Nb, dtype);
+    g.A = T; g.Bm = dY; g.C = dX;
+    g.M = Ci; g.N = L; g.K = Co;
+    g.a_kc = false; g.a_ld = Ci; g.a_g0 = (int64_t)Nb * Co * Ci; g.a_g1 = (int64_t)Co * Ci;
+    g.b_kc = false; g.b_ld = dys[2]; g.b_g0 = dys[0]; g.b_g1 = dys[1];
+    g.c_ld = dxs[2]; g.c_g0 = dxs[0]; g.c_g1 = dxs[1];
+    const int rc = gemm_launch(g, st);
+    if (rc != HFTA_OK) return rc;
+  }
+  if (dT) {      // dT[o][c] = sum_l dY[o][l] X[c][l], per sample: no reduction over the batch
+    GemmDesc g = head_desc(B, 1, Nb, dtype);
+    g.A = dY; g.Bm = X; g.C = dT;
+    g.M = Co; g.N = Ci; g.K = L;
+    g.a_kc = true; g.a_ld = dys[2]; g.a_g0 = dys[0]; g.a_g1 = dys[1];
+    g.b_kc = true; g.b_ld = xs[2]; g.b_g0 = xs[0]; g.b_g1 = xs[1];
+    g.c_ld = Ci; g.c_g0 = (int64_t)Nb * Co * Ci; g.c_g1 = (int64_t)Co * Ci;
+    return gemm_launch(g, st);
+  }
+  return HFTA_OK;
+}
+
 }  // extern "C"

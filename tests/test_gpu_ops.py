@@ -729,3 +729,24 @@ def test_conv1x1_bn_maxpool_fwd_bwd_one_operator(hb, B, Nb, Ci, Co, L, act):
                               sx, dW2, dB0, dG, dBt, act, slope, ws)
     check(host(dX2), rdx, TOL[dtype], "dX (moments recomputed)")
     check(host(dW2), rdw, 2e-4, "dW (moments recomputed)")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,Ci,Co,L", [(2, 3, 3, 3, 300), (2, 4, 64, 64, 260), (3, 2, 24, 40, 131)])
+def test_point_transform(hb, dtype, B, Nb, Ci, Co, L):
+    """Per-sample matrices applied to the points (3x3 input transform, 64x64 feature transform)."""
+    print(f"point transform {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} L={L}", flush=True)
+    x = hi.normal(231, (Nb, B * Ci, L), dtype)
+    t = hi.normal(232, (B, Nb, Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    dy = hi.normal(233, (Nb, B * Co, L), dtype)
+    X, T, dY = dev(x, dtype), dev(t, dtype), dev(dy, dtype)
+    xs, ys = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    Y, dX, dT = empty((Nb, B * Co, L), dtype), empty((Nb, B * Ci, L), dtype), empty((B, Nb, Co, Ci), dtype)
+    hb.point_transform_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, T, Y, ys)
+    hb.point_transform_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, T, dY, ys, dX, xs, dT)
+    for b in range(B):
+        xb, dyb = x[:, b * Ci:(b + 1) * Ci], dy[:, b * Co:(b + 1) * Co]
+        check(host(Y)[:, b * Co:(b + 1) * Co], oops.point_transform_fwd(xb, t[b]), TOL[dtype], "Y")
+        rdx, rdt = oops.point_transform_bwd(xb, t[b], dyb)
+        check(host(dX)[:, b * Ci:(b + 1) * Ci], rdx, TOL[dtype], "dX")
+        check(host(dT)[b], rdt, TOL[dtype], "dT")

@@ -486,3 +486,19 @@ def test_adadelta_and_steplr_vs_library_and_closed_forms():
             assert abs(ops.steplr(base, gam, step, epoch)[b] - o.param_groups[0]["lr"]) <= 1e-12 * base[b]
             o.step()
             sch.step()
+
+
+def test_point_transform_bruteforce_and_adjoints():
+    N, Ci, Co, L = 2, 3, 4, 5
+    x, t, dy = rnd(N, Ci, L), rnd(N, Co, Ci), rnd(N, Co, L)
+    y = ops.point_transform_fwd(x, t)
+    for n in range(N):
+        for o in range(Co):
+            for l in range(L):
+                assert abs(y[n, o, l] - sum(t[n, o, c] * x[n, c, l] for c in range(Ci))) < 1e-13
+    dx, dt = ops.point_transform_bwd(x, t, dy)
+    close(dx, fd_grad(lambda q: float((ops.point_transform_fwd(q, t) * dy).sum()), x), 1e-6)
+    close(dt, fd_grad(lambda q: float((ops.point_transform_fwd(x, q) * dy).sum()), t), 1e-6)
+    # samples do not mix: changing sample 1's matrix leaves sample 0's output untouched
+    t2 = t.copy(); t2[1] += 1.0
+    assert np.array_equal(ops.point_transform_fwd(x, t2)[0], y[0])
