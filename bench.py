@@ -91,7 +91,7 @@ def kernel_label(name, a):
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci <= 4 and L % 4 == 0:
             return "conv1x1_tinyk_kernel"
-        if dt == 1 and Ci <= 128 and Ci % 8 == 0 and Co >= 64 and L % 4 == 0:
+        if dt == 1 and Ci % 8 == 0 and L % 4 == 0 and ((Ci <= 128 and Co >= 64) or (Ci <= 256 and Co >= 512)):
             return "conv1x1_stream_kernel"
         if dt == 1 and big_gemm(B * Nb, Co, L, Ci):
             return "gemm_big_kernel(fwd)"
@@ -105,7 +105,7 @@ def kernel_label(name, a):
         if a[8] is not None:
             return ("gemm_big_kernel" if dt == 1 and big_gemm(B, M, Fx, Fy) else "gemm_pf_kernel") + "(dX)"
         if a[9] is not None:
-            return ("gemm_big_kernel" if dt == 1 and big_gemm(B, Fx, Fy, M) else "gemm_pf_kernel") + "(dW)"
+            return ("gemm_big_kernel" if dt == 1 and big_gemm_split(B, Fx, Fy, M) else "gemm_pf_kernel") + "(dW)"
         return "colsum_kernel"
     if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
@@ -131,9 +131,12 @@ def kernel_label(name, a):
         B, Nb, Ci, Co, L, dt = a[:6]
         k = "gemm_pf_kernel" if dt == 1 else "gemm_kernel"
         if a[11] is not None:
-            if dt == 1 and Co <= 128 and Co % 8 == 0 and Ci >= 64 and L % 4 == 0 and a[15] is not None:
+            if (dt == 1 and Co % 8 == 0 and L % 4 == 0 and a[15] is not None
+                    and ((Co <= 128 and Ci >= 64) or (Co <= 256 and Ci >= 512))):
                 return "conv1x1_stream_kernel(dX)"
             return ("gemm_big_kernel" if dt == 1 and big_gemm(B * Nb, Ci, L, Co) else k) + "(dX)"
+        if dt == 1 and big_gemm_split(B, Co, Ci, L, Nb):
+            k = "gemm_big_kernel"
         return k + "(dW)+splitk_reduce_kernel"
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
@@ -147,7 +150,16 @@ def kernel_label(name, a):
 
 def big_gemm(G, M, N, K):
     """The 256x256-tile kernel's dispatch rule (compute-bound shapes)."""
-    return M >= 192 and N >= 192 and K >= 512 and ((M + 255) // 256) * ((N + 255) // 256) * G >= 192
+    return M >= 192 and N >= 192 and K >= 256 and ((M + 255) // 256) * ((N + 255) // 256) * G >= 192
+
+
+def big_gemm_split(G, M, N, K, S=1):
+    """Weight-gradient shapes that run split over k on the 256x256-tile kernel: some split count
+    keeps at least 16 k-tiles per workgroup and gives at least 192 workgroups."""
+    if M < 192 or N < 192 or K < 256:
+        return False
+    t256, tt = ((M + 255) // 256) * ((N + 255) // 256) * G, S * ((K + 63) // 64)
+    return tt >= 32 and any(t256 * s >= 192 for s in range(1, 33) if tt // s >= 16)
 
 
 def algorithmic_flops(name, a):

@@ -1,7 +1,8 @@
-// Streaming forward kernel of the fused k=1 Conv1d for layers with at most 128 input channels
+// Streaming forward kernel of the fused k=1 Conv1d for layers with at most 128 (256) input channels
 // (fusion rules table, Conv1d row; the point-cloud models' 64 -> 64 ... 128 -> 1024 layers).
 //
-// Per model b and sample n:  Y[co][l] = sum_ci W[b][co][ci] * X[ci][l] + bias[b][co], with Ci <= 128:
+// Per model b and sample n:  Y[co][l] = sum_ci W[b][co][ci] * X[ci][l] + bias[b][co], with Ci <= 128
+// (<= 256 for layers at least 512 channels wide, e.g. the data gradient of a 2880 -> 256 layer):
 // the whole reduction fits one LDS tile, so a generic k-loop kernel spends its time in launch,
 // prologue and epilogue latencies, not in the matrix cores or in HBM.  Here one workgroup owns one
 // 128-point slice of one sample, keeps that X tile (transposed, [point][ci]) in LDS, and walks
@@ -13,6 +14,10 @@
 #include "gemm_pf.h"
 
 namespace hfta {
+
+// 128 < Ci <= 256 keeps a 256-deep X tile and W tile in LDS (one workgroup per compute unit): it
+// beats the k-loop GEMM only when many W tiles share one X tile.
+constexpr int STREAM_WIDE_MIN_CO = 512;
 
 struct StreamArgs {
   const bf16_raw* W;
@@ -147,7 +152,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv1x1_stream_kernel(StreamArgs
 int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
                        const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st) {
   auto al = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; };
-  if (Ci > 128 || Ci % 8 != 0 || Co < 64 || L % 4 != 0) return HFTA_EUNSUPPORTED;
+  if (Ci > 256 || Ci % 8 != 0 || Co < 64 || L % 4 != 0) return HFTA_EUNSUPPORTED;
+  if (Ci > 128 && Co < STREAM_WIDE_MIN_CO) return HFTA_EUNSUPPORTED;
   if (act == HFTA_ACT_TANH || act == HFTA_ACT_GELU) return HFTA_EUNSUPPORTED;
   if (!al(W, 16) || !al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0) return HFTA_EUNSUPPORTED;
   const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2, w_ext = (int64_t)Co * Ci * 2;
@@ -167,7 +173,8 @@ int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, cons
   a.w_extent = (uint32_t)w_ext; a.x_extent = (uint32_t)x_ext;
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
   if (Ci <= 64) hipLaunchKernelGGL(conv1x1_stream_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
-  else hipLaunchKernelGGL(conv1x1_stream_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);
+  else if (Ci <= 128) hipLaunchKernelGGL(conv1x1_stream_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);
+  else hipLaunchKernelGGL(conv1x1_stream_kernel<256>, grid, dim3(GEMM_THREADS), 0, st, a);
   return launch_status();
 }
 

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   if (q == 0 && i < count) out[i] = (sh[0][li] + sh[1][li]) + (sh[2][li] + sh[3][li]);
 }
 
-int gemm_big_launch(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStream_t st);
+int gemm_big_launch(const GemmDesc& d, const GemmArgs& a, bool v16, dim3 grid, hipStream_t st);
 
 static inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -31,9 +31,34 @@ static int total_tiles(const GemmDesc& d) {
   return d.S * ((d.K + BK - 1) / BK);
 }
 
+// 256x256-tile kernel: one workgroup per compute unit at a time, so a launch runs in rounds of 256
+// workgroups.  Cost model per split count s: rounds * (k-tiles per workgroup + a fixed prologue /
+// epilogue, in k-tile units) + the partial buffer's write and read; the cheapest s wins.
+// shortest reduction (per split) the 256x256-tile kernel is used for
+constexpr int BIG_MIN_K = 256;
+static int pick_splits_big(const GemmDesc& d) {
+  if (d.dtype != HFTA_BF16 || d.M < 192 || d.N < 192 || d.K < 256) return 0;
+  const int64_t t256 = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.G0 * d.G1;
+  const int64_t tt = (int64_t)d.S * ((d.K + 63) / 64);
+  if (tt < 32) return 0;
+  const double fixed = 4.0;                                   // prologue + epilogue, in k-tiles
+  const double per_split = 0.2 * (double)t256 / 256.0;        // partial traffic of one more split
+  int best = 0;
+  double best_cost = 0.0;
+  for (int s = 1; s <= 32 && tt / s >= 16; ++s) {
+    if (t256 * s < 192) continue;
+    const double rounds = (double)((t256 * s + 255) / 256);
+    const double cost = rounds * ((double)tt / s + fixed) + (s > 1 ? per_split * s : 0.0);
+    if (best == 0 || cost < best_cost) { best = s; best_cost = cost; }
+  }
+  return best;
+}
+
 // Enough workgroups to fill 256 compute units a few times over, without cutting
 // the reduction into pieces shorter than 8 k-tiles.
 int gemm_pick_splits(const GemmDesc& d) {
+  const int big = pick_splits_big(d);
+  if (big > 0) return big;
   const int64_t tiles = (int64_t)((d.M + GEMM_BM - 1) / GEMM_BM) * ((d.N + GEMM_BN - 1) / GEMM_BN) * d.G0 * d.G1;
   const int tt = total_tiles(d);
   if (tiles >= 512 || tt < 16) return 1;
@@ -63,6 +88,13 @@ static int launch_layout(const GemmDesc& d, const GemmArgs& a, dim3 grid, hipStr
   else if (d.a_kc && d.b_kc) launch_typed<T, true, true>(d, a, grid, st);
   else if (!d.a_kc && !d.b_kc) launch_typed<T, false, false>(d, a, grid, st);
   else return HFTA_EUNSUPPORTED;
+  return launch_status();
+}
+
+static int reduce_partials(const GemmDesc& d, int64_t G, int splits, hipStream_t st) {
+  const int64_t count = G * (int64_t)d.M * d.N;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st,
+                     d.partial, reinterpret_cast<float*>(d.C), count, splits);
   return launch_status();
 }
 
@@ -145,17 +177,18 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   // Compute-bound problems (MLP-sized bf16 GEMMs) take the 256x256 kernel: it needs 16-byte
   // loadable operands, no split, a long reduction, and enough tiles to give every compute unit
   // at least one.
-  if ((v16 || (v8 && !d.a_kc && !d.b_kc)) && splits == 1 && d.M >= 192 && d.N >= 192 && d.K >= 512 &&
+  if ((v16 || (v8 && d.a_kc == d.b_kc)) && d.M >= 192 && d.N >= 192 && d.K >= 256 && (int64_t)d.K * d.S >= BIG_MIN_K * (int64_t)splits &&
       (d.c_seg == 0 || a.c_vec >= 8)) {
     const int64_t t256 = (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * G;
-    if (t256 >= 192) {
+    if (t256 * splits >= 192) {
       GemmArgs b = a;
       b.tiles_m = (d.M + 255) / 256;
       b.tiles_n = (d.N + 255) / 256;
       b.tiles_per_seg = (d.K + 63) / 64;
       b.total_tiles = d.S * b.tiles_per_seg;
-      dim3 grid((unsigned)(b.tiles_m * b.tiles_n), 1, (unsigned)G);
-      const int rc = gemm_big_launch(d, b, grid, st);
+      dim3 grid((unsigned)(b.tiles_m * b.tiles_n), 1, (unsigned)(G * splits));
+      const int rc = gemm_big_launch(d, b, v16 || !(d.a_kc || d.b_kc), grid, st);
+      if (rc == HFTA_OK && splits > 1) return reduce_partials(d, G, splits, st);
       if (rc != HFTA_EUNSUPPORTED) return rc;
     }
   }
@@ -172,12 +205,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
     rc = d.dtype == HFTA_BF16 ? launch_layout<bf16_raw>(d, a, grid, st) : launch_layout<float>(d, a, grid, st);
   }
   if (rc != HFTA_OK) return rc;
-  if (splits > 1) {
-    const int64_t count = G * (int64_t)d.M * d.N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st,
-                       d.partial, reinterpret_cast<float*>(d.C), count, splits);
-    return launch_status();
-  }
+  if (splits > 1) return reduce_partials(d, G, splits, st);
   return HFTA_OK;
 }
 

@@ -204,7 +204,10 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
   }
   const int tile_m = bx % p.tiles_m, tile_n = bx / p.tiles_m;
   const int m0 = tile_m * BIG_BM, n0 = tile_n * BIG_BN;
-  const int g0 = bz / p.G1, g1 = bz % p.G1;
+  // split-K: this workgroup reduces k-tiles [t_begin, t_end) and writes an fp32 partial tile
+  const int split = bz % p.splits, g = bz / p.splits;
+  const int g0 = g / p.G1, g1 = g % p.G1;
+  const int t_begin = (int)((int64_t)p.total_tiles * split / p.splits);
   const bf16_raw* Ab = reinterpret_cast<const bf16_raw*>(p.A) + g0 * p.a_g0 + g1 * p.a_g1;
   const bf16_raw* Bb = reinterpret_cast<const bf16_raw*>(p.Bm) + g0 * p.b_g0 + g1 * p.b_g1;
 
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
   ob.init(n0, p.N, p.b_ld, t);
   typename BigOp<A_KC, V16>::Regs ra[BIG_PF];
   typename BigOp<B_KC, V16>::Regs rb[BIG_PF];
-  const int t_end = p.total_tiles;
+  const int t_end = (int)((int64_t)p.total_tiles * (split + 1) / p.splits);
   auto issue = [&](int set, int tt) {
     const bool live = tt < t_end;
     const int Ke = live ? p.K : 0;      // a dead tile has no valid k: every offset out of range
@@ -236,14 +239,14 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
   auto tileB = [&](int buf) { return smem + buf * 2 * BIG_TILE + BIG_TILE; };
 
 #pragma unroll
-  for (int d = 0; d < BIG_PF; ++d) issue(d, d);
+  for (int d = 0; d < BIG_PF; ++d) issue(d, t_begin + d);
   oa.store(tileA(0), ra[0], t);
   ob.store(tileB(0), rb[0], t);
   __syncthreads();
   int buf = 0;
   const int r = lane & 31, gsel = lane >> 5;
   bool done = false;
-  for (int base = 0; !done; base += BIG_PF) {
+  for (int base = t_begin; !done; base += BIG_PF) {
 #pragma unroll
     for (int d = 0; d < BIG_PF; ++d) {
       const int cur = base + d;
@@ -278,7 +281,13 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
   constexpr int ES = sizeof(OutT);
   constexpr int RP = ES == 2 ? 128 : 64;
   constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
-  OutT* Cb = reinterpret_cast<OutT*>(p.C) + g0 * p.c_g0 + g1 * p.c_g1;
+  const bool to_partial = ES == 4 && p.splits > 1;
+  OutT* Cb = to_partial
+      ? reinterpret_cast<OutT*>(p.partial) + ((int64_t)split * (gridDim.z / p.splits) + g) * (int64_t)p.M * p.N
+      : reinterpret_cast<OutT*>(p.C) + g0 * p.c_g0 + g1 * p.c_g1;
+  const int64_t c_ld = to_partial ? p.N : p.c_ld;
+  const int c_vec = to_partial ? p.p_vec : p.c_vec;
+  const int c_seg = to_partial ? 0 : p.c_seg;
   const bf16_raw* bias = p.bias ? reinterpret_cast<const bf16_raw*>(p.bias) + g0 * p.bias_g0 + g1 * p.bias_g1 : nullptr;
   const int ml = lane & 31, nq = (lane >> 5) * 4;
   const float neg_slope = p.slope;
@@ -332,7 +341,7 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
       }
     }
     __syncthreads();
-    big_store_rows<OutT, BIG_THREADS>(smem, Cb, p.c_ld, p.M, p.N, m0 + pass * RP, n0, p.c_vec, t, p.c_seg, p.c_seg_stride);
+    big_store_rows<OutT, BIG_THREADS>(smem, Cb, c_ld, p.M, p.N, m0 + pass * RP, n0, c_vec, t, c_seg, p.c_seg_stride);
     if (pass + 1 < 256 / RP) __syncthreads();
   }
 }

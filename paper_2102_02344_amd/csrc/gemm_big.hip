@@ -8,15 +8,22 @@ static void launch_big(const GemmArgs& a, dim3 grid, hipStream_t st) {
   hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, OutT, true, COLB, ACT>), grid, dim3(BIG_THREADS), 0, st, a);
 }
 
-// `a` must carry tile counts for 256x256 tiles and 64-element k-tiles, operand extents, and 16-byte
-// loadable k-contiguous operands.  HFTA_EUNSUPPORTED: not a combination this kernel is built for.
-int gemm_big_launch(const GemmDesc& d, const GemmArgs& a0, dim3 grid, hipStream_t st) {
+// `a` must carry tile counts for 256x256 tiles and 64-element k-tiles and operand extents.
+// `v16`: k-contiguous operands are loadable in 16-byte pieces; otherwise (rows only 8-byte aligned,
+// e.g. 2500 points per sample) only the weight-gradient form (both operands k-contiguous, fp32
+// output) is built, on 8-byte loads.  HFTA_EUNSUPPORTED: not a combination this kernel is built for.
+int gemm_big_launch(const GemmDesc& d, const GemmArgs& a0, bool v16, dim3 grid, hipStream_t st) {
   GemmArgs a = a0;
   const bool colb = d.bias && d.bias_mode == 2;
   const bool sel = d.act == HFTA_ACT_NONE || d.act == HFTA_ACT_RELU || d.act == HFTA_ACT_LEAKY;
   a.slope = d.act == HFTA_ACT_NONE ? 1.f : d.act == HFTA_ACT_RELU ? 0.f : d.slope;
   if (colb && (reinterpret_cast<uintptr_t>(d.bias) % 8 != 0 || d.bias_g0 % 4 != 0 || d.bias_g1 % 4 != 0 || d.N % 4 != 0))
     return HFTA_EUNSUPPORTED;
+  if (!v16) {
+    if (!(d.out_f32 && d.a_kc && d.b_kc) || colb || !sel) return HFTA_EUNSUPPORTED;
+    hipLaunchKernelGGL((gemm_big_kernel<true, true, float, false, false, BIG_SEL>), grid, dim3(BIG_THREADS), 0, st, a);
+    return launch_status();
+  }
   if (d.out_f32) {
     if (colb || !sel) return HFTA_EUNSUPPORTED;
     if (d.a_kc && !d.b_kc) launch_big<true, false, float, false, BIG_SEL>(a, grid, st);

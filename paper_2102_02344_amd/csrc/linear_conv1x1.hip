@@ -304,10 +304,10 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
   return gemm_launch(d, as_stream(stream));
 }
 
-// The data gradient of a narrow layer (Co <= 128) is a k=1 convolution of dY with the transposed
+// The data gradient of a narrow layer (Co <= 128, or Co <= 256 under at least 512 inputs) is a k=1 convolution of dY with the transposed
 // weights: it takes the streaming forward kernel once W^T [B][Ci][Co] has been written to the workspace.
 static bool dx_streams(int Ci, int Co, int L, int dtype) {
-  return dtype == HFTA_BF16 && Co <= 128 && Co % 8 == 0 && Ci >= 64 && L % 4 == 0;
+  return dtype == HFTA_BF16 && Co % 8 == 0 && L % 4 == 0 && ((Co <= 128 && Ci >= 64) || (Co <= 256 && Ci >= 512));
 }
 static size_t wt_offset(size_t partial_bytes) { return (partial_bytes + 255) & ~(size_t)255; }
 

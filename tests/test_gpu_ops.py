@@ -83,7 +83,8 @@ def test_linear_identity_and_B1(hb):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Nb,Ci,Co,L", [(3, 2, 70, 150, 300), (2, 3, 3, 64, 250), (2, 2, 128, 40, 129),
                                           (2, 4, 64, 64, 500), (2, 3, 3, 64, 1300), (3, 2, 4, 24, 132),
-                                          (2, 2, 128, 64, 260)])
+                                          (2, 2, 128, 64, 260), (2, 2, 256, 520, 260), (2, 2, 520, 256, 132),
+                                          (1, 2, 200, 512, 132)])
 def test_conv1x1_fwd_bwd(hb, dtype, B, Nb, Ci, Co, L):
     print(f"conv1x1 {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} L={L}", flush=True)
     x = hi.normal(11, (Nb, B * Ci, L), dtype)
@@ -109,6 +110,44 @@ def test_conv1x1_fwd_bwd(hb, dtype, B, Nb, Ci, Co, L):
     dW2 = empty((B * Co, Ci), torch.float32)
     hb.conv1x1_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, dY, ys, None, None, dW2, None, ws)
     assert torch.equal(dW, dW2)
+
+
+@pytest.mark.parametrize("L", [1028, 1040])
+def test_weight_gradient_split_reduction_on_large_tiles(hb, L):
+    """Few large output tiles and a long reduction: the weight gradient runs split over k on the
+    256x256-tile kernel (ragged Co, ragged last k-tile, splits that cross sample boundaries; rows of
+    L points 8- or 16-byte aligned) and its fixed-order reduction; Linear case: one segment."""
+    dtype = "bf16"
+    B, Nb, Ci, Co = 3, 16, 512, 500
+    print(f"conv1x1 dW large tiles B={B} Nb={Nb} Ci={Ci} Co={Co} L={L}", flush=True)
+    x = hi.normal(21, (Nb, B * Ci, L), dtype)
+    w = hi.normal(22, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    dy = hi.normal(23, (Nb, B * Co, L), dtype)
+    X, W, dY = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
+    xs, ys = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    dW = empty((B * Co, Ci), torch.float32)
+    nws = hb.conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype])
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    hb.conv1x1_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, dY, ys, None, None, dW, None, ws)
+    _, rdw, _ = oa.conv1x1_bwd(B, x, w, dy)
+    check(host(dW), rdw, f32_tol(dtype), "dW")
+    dW2 = empty((B * Co, Ci), torch.float32)
+    hb.conv1x1_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, dY, ys, None, None, dW2, None, ws)
+    assert torch.equal(dW, dW2)
+
+    B, M, Fx, Fy = 4, 8200, 512, 760
+    print(f"linear dW large tiles B={B} M={M} Fx={Fx} Fy={Fy}", flush=True)
+    x = hi.normal(24, (B, M, Fx), dtype)
+    w = hi.normal(25, (B, Fx, Fy), dtype, 1.0 / np.sqrt(Fx))
+    dy = hi.normal(26, (B, M, Fy), dtype)
+    dW = empty((B, Fx, Fy), torch.float32)
+    nws = hb.linear_bwd_workspace_bytes(B, M, Fx, Fy, DT[dtype])
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    hb.linear_bwd(B, M, Fx, Fy, DT[dtype], dev(x, dtype), dev(w, dtype), dev(dy, dtype), None, dW, None, ws)
+    _, rdw, _ = oa.linear_bwd(B, x, w, dy)
+    check(host(dW), rdw, f32_tol(dtype), "linear dW")
 
 
 def test_conv1x1_cross_talk_and_linear_special_case(hb):
