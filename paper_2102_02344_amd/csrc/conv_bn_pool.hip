@@ -626,6 +626,13 @@ size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
 //     the activated value is the argmax of  sign(gamma_c) (W_c x):  one pass of the matrix product
 //     with sign-folded weights, a running (max, first argmax) per channel and tile, nothing stored.
 // =====================================================================================================
+// max of three without the quieting moves of fmaxf (inputs are matrix-instruction results)
+__device__ __forceinline__ float fmax3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 struct FbpArgs {
   const bf16_raw* X; const bf16_raw* W; const bf16_raw* bias;
   const float* gamma; const float* beta;
@@ -799,35 +806,40 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[j][s], a[i], acc[i][j], 0, 0, 0);
     }
     // lane = channel wm*64 + i*32 + (lane & 31); its 32 points wn*64 + j*32 + 8q + 4(lane>>5) + e in rising order
+    // Two passes per channel: the maximum of the lane's 32 values (no index carried), then the
+    // first position that holds it, walking the positions downwards so the lowest one is kept.
     float bv[2];
     int bp[2];
     const int pt0 = wn * 64 + 4 * gsel;
-    if (lim >= 128) {
+    if (lim < 128) {                       // the last slice: points past L do not take part
+      int room = lim - pt0;                // opaque to the optimizer: 64 loop-invariant lane masks
+      asm volatile("" : "+v"(room));       // would otherwise be kept (and spilled) across the loop
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        bv[i] = -INFINITY; bp[i] = 0;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float val = acc[i][j][v];
-            const int pt = pt0 + j * 32 + 8 * (v >> 2) + (v & 3);
-            if (val > bv[i]) { bv[i] = val; bp[i] = pt; }
-          }
-      }
-    } else {                             // the last slice: points past L do not take part
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        bv[i] = -INFINITY; bp[i] = 0;
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int pt = pt0 + j * 32 + 8 * (v >> 2) + (v & 3);
-            const float val = pt < lim ? acc[i][j][v] : -INFINITY;
-            if (val > bv[i]) { bv[i] = val; bp[i] = pt; }
-          }
-      }
+          for (int v = 0; v < 16; ++v)
+            if (j * 32 + 8 * (v >> 2) + (v & 3) >= room) acc[i][j][v] = -INFINITY;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      float m[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        m[q] = fmax3(acc[i][q >> 2][4 * (q & 3)], acc[i][q >> 2][4 * (q & 3) + 1],
+                     fmax3(acc[i][q >> 2][4 * (q & 3) + 2], acc[i][q >> 2][4 * (q & 3) + 3], -INFINITY));
+      bv[i] = fmax3(fmax3(m[0], m[1], m[2]), fmax3(m[3], m[4], m[5]), fmax3(m[6], m[7], -INFINITY));
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int rel = 0;
+#pragma unroll
+      for (int j = 1; j >= 0; --j)
+#pragma unroll
+        for (int v = 15; v >= 0; --v)
+          rel = acc[i][j][v] == bv[i] ? j * 32 + 8 * (v >> 2) + (v & 3) : rel;
+      bp[i] = pt0 + rel;
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {        // the two lane halves hold interleaved groups of four points

@@ -65,3 +65,84 @@ def test_validation_precedes_launch(lib):
     assert raw.hfta_dropout(8, 0, one, one, 1.0, one, None) == lib.EINVAL
     assert raw.hfta_act_bwd(8, 0, one, one, one, lib.ACT_GELU, 0.0, 1, None) == lib.EUNSUPPORTED
     assert raw.hfta_layernorm_bwd(1, 4, 8, 0, one, one, one, one, one, one, one, one, None, 0, None) == lib.EWORKSPACE
+
+
+def test_validation_of_the_wider_entry_points(lib):
+    """One-operator tail, segmentation support operators, Adadelta / StepLR, Embedding / attention,
+    point transform: bad arguments come back as status codes before anything is launched."""
+    raw = lib.raw()
+    one = C.c_void_p(256)
+    s4 = (C.c_int64 * 4)(128 * 2500, 8 * 128 * 2500, 2500, 1)
+    bad_l = (C.c_int64 * 4)(128 * 2500, 8 * 128 * 2500, 2500, 2)
+    v3 = (C.c_int64 * 3)(32 * 1024, 1024, 1)
+    # ---- conv + BatchNorm + max over points as one operator
+    assert raw.hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(8, 32, 128, 1024, 2500, 1) > 0
+    assert raw.hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(8, 32, 128, 1024, 2500, 0) == 0      # fp32: not built
+    assert raw.hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(8, 32, 136, 1024, 2500, 1) == 0      # Ci > 128
+    assert raw.hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(8, 32, 128, 1024, 2502, 1) == 0      # L % 4
+    assert raw.hfta_conv1x1_bn_maxpool_saved_floats(8, 128, 1024) == 8 * (128 * 128 + 128 + 1024 * 128)
+
+    def tail_fwd(B=8, Nb=32, Ci=128, Co=1024, L=2500, dt=1, X=one, xs=s4, act=1, ws=one, nws=1 << 40):
+        return raw.hfta_conv1x1_bn_maxpool_fwd(B, Nb, Ci, Co, L, dt, X, xs, one, None, one, one, 1e-5, 0.1, None,
+                                               None, one, one, one, one, v3, one, None, act, 0.0, ws, nws, None)
+    assert tail_fwd(X=None) == lib.EINVAL
+    assert tail_fwd(B=0) == lib.EINVAL
+    assert tail_fwd(dt=0) == lib.EUNSUPPORTED
+    assert tail_fwd(Ci=136) == lib.EUNSUPPORTED
+    assert tail_fwd(Co=1032) == lib.EUNSUPPORTED
+    assert tail_fwd(L=2502) == lib.EUNSUPPORTED
+    assert tail_fwd(xs=bad_l) == lib.EUNSUPPORTED
+    assert tail_fwd(act=lib.ACT_TANH) == lib.EUNSUPPORTED
+    assert tail_fwd(ws=None, nws=0) == lib.EWORKSPACE
+    assert tail_fwd(nws=1024) == lib.EWORKSPACE
+
+    def tail_bwd(Z=None, zhit=one, ws=one, nws=1 << 40, dt=1):
+        return raw.hfta_conv1x1_bn_maxpool_bwd(8, 32, 128, 1024, 2500, dt, one, s4, one, None, Z, s4 if Z else None,
+                                               zhit, None, one, one, v3, one, one, one, one, one, s4, one, None,
+                                               one, one, 1, 0.0, ws, nws, None)
+    assert tail_bwd(Z=one, zhit=one) == lib.EINVAL            # exactly one of Z / zhit
+    assert tail_bwd(Z=None, zhit=None) == lib.EINVAL
+    assert tail_bwd(dt=0) == lib.EUNSUPPORTED
+    assert tail_bwd(ws=None, nws=0) == lib.EWORKSPACE
+
+    # ---- strided support operators of the segmentation head
+    c3 = (C.c_int64 * 3)(16 * 64, 64, 1)
+    assert raw.hfta_add_sample_bias(1, 2, 64, 0, 1, one, s4, one, c3, one, s4, None) == lib.EINVAL
+    assert raw.hfta_add_sample_bias(1, 2, 64, 8, 1, one, bad_l, one, c3, one, s4, None) == lib.EUNSUPPORTED
+    assert raw.hfta_sum_points(1, 2, 64, 8, 1, None, s4, one, c3, None) == lib.EINVAL
+    assert raw.hfta_add_strided(1, 2, 64, 8, 9, one, s4, one, s4, one, s4, None) == lib.EINVAL
+    assert raw.hfta_maxpool_points_bwd_add(1, 2, 64, 8, 1, one, None, c3, one, s4, None) == lib.EINVAL
+    need = raw.hfta_softmax_xent_points_workspace_bytes(6, 16, 2500)
+    assert need > 0
+    assert raw.hfta_softmax_xent_points(6, 16, 50, 2500, 1, one, s4, one, one, one, s4, one, need - 1,
+                                        None) == lib.EWORKSPACE
+    assert raw.hfta_softmax_xent_points(6, 16, 0, 2500, 1, one, s4, one, one, one, s4, one, need, None) == lib.EINVAL
+
+    # ---- Adadelta and the step schedule
+    offs = (C.c_int64 * 3)(0, 8, 24)
+    bad_offs = (C.c_int64 * 3)(0, 8, 8)
+    assert raw.hfta_adadelta_step_multi(0, 2, offs, 0, one, one, one, one, None, one, one, one, one, None) == lib.EINVAL
+    assert raw.hfta_adadelta_step_multi(2, 2, bad_offs, 0, one, one, one, one, None, one, one, one, one,
+                                        None) == lib.EINVAL
+    assert raw.hfta_adadelta_step_multi(2, 2, offs, 0, one, one, None, one, None, one, one, one, one, None) == lib.EINVAL
+    assert raw.hfta_adadelta_step_multi(2, 10 ** 6, offs, 0, one, one, one, one, None, one, one, one, one,
+                                        None) in (lib.EINVAL, lib.EUNSUPPORTED)
+    assert raw.hfta_steplr(0, one, one, one, 3, one, None) == lib.EINVAL
+    assert raw.hfta_steplr(4, one, one, one, -1, one, None) == lib.EINVAL
+    assert raw.hfta_steplr(4, one, None, one, 3, one, None) == lib.EINVAL
+
+    # ---- Embedding, attention core, wide-class cross-entropy, per-sample point transform
+    assert raw.hfta_embedding_fwd(2, 64, 0, 32, 1, one, one, 1.0, None, 0, one, None) == lib.EINVAL
+    assert raw.hfta_embedding_bwd(2, 7681, 100, 32, 1, one, one, 1.0, one, None) == lib.EUNSUPPORTED
+    assert raw.hfta_attention_fwd(2, 4, 16, 30, 4, 1, one, one, one, 1, None) == lib.EINVAL          # E % H
+    assert raw.hfta_attention_fwd(64, 128, 16, 32, 16, 1, one, one, one, 1, None) == lib.EUNSUPPORTED  # B*N*H
+    need = raw.hfta_attention_bwd_workspace_bytes(2, 4, 16, 32, 4, 1)
+    assert need > 0
+    assert raw.hfta_attention_bwd(2, 4, 16, 32, 4, 1, one, one, one, one, one, need - 1, None) == lib.EWORKSPACE
+    need = raw.hfta_softmax_xent_rows_workspace_bytes(2, 64)
+    assert need > 0
+    assert raw.hfta_softmax_xent_rows(2, 64, 1000, 1, one, one, one, one, None, 0, None) == lib.EWORKSPACE
+    assert raw.hfta_softmax_xent_rows(2, 64, 0, 1, one, one, one, one, one, need, None) == lib.EINVAL
+    assert raw.hfta_point_transform_fwd(1, 2, 64, 64, 8, 1, one, bad_l, one, one, s4, None) == lib.EUNSUPPORTED
+    assert raw.hfta_point_transform_fwd(300, 300, 64, 64, 8, 1, one, s4, one, one, s4, None) == lib.EUNSUPPORTED
+    assert raw.hfta_point_transform_bwd(1, 2, 64, 64, 8, 1, one, s4, one, None, s4, one, s4, one, None) == lib.EINVAL
