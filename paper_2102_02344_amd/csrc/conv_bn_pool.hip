@@ -648,20 +648,28 @@ struct FbpArgs {
 };
 
 // One workgroup owns a 128-point slice of one sample; each wavefront keeps its half of the X tile
-// as matrix-instruction fragments in registers, the loop walks the 128-row tiles of W through two
+// as matrix-instruction fragments in registers, the loop walks the RT-row tiles of W through two
 // LDS buffers (tile ct+1 parked, tile ct+2 in flight in registers while tile ct is multiplied: one
-// barrier per step), and the epilogue of a step is a per-lane scan of the accumulators for
-// (max, first argmax) instead of a store.
-template <int KT>
-__global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) {   // two wavefronts per SIMD
+// barrier per step), and the epilogue of a step is a per-lane search of the accumulators for
+// (max, first argmax) instead of a store.  RT = 64: 32 accumulators and 16 in-flight W registers
+// per lane (140 registers) and 36 KB of LDS, so three workgroups share a compute unit and cover each
+// other's phases (128-row tiles: 201 registers, two workgroups, 10 % slower).
+#ifndef FBP_RT
+#define FBP_RT 64
+#endif
+#ifndef FBP_OCC
+#define FBP_OCC 3
+#endif
+template <int KT, int RT>
+__global__ __launch_bounds__(GEMM_THREADS, FBP_OCC) void fbp_main_kernel(FbpArgs p) {
   constexpr int PITCH = KT * 2 + 16;
-  constexpr int TILE = 128 * PITCH;
+  constexpr int XTILE = 128 * PITCH;
+  constexpr int WTILE = RT * PITCH;
   constexpr int SUB = KT / 32;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE];
-  __shared__ float pm_v[2][2][128];                    // [step parity][point half][channel]
-  __shared__ int pm_p[2][2][128];
-  unsigned char* Xs = smem;
-  unsigned char* Ws = smem + TILE;
+  constexpr int H = RT / 64;                            // 64-row passes of the W tile load; 32-row blocks per wavefront
+  __shared__ __attribute__((aligned(16))) unsigned char smem[XTILE > 2 * WTILE ? XTILE : 2 * WTILE];
+  __shared__ float pm_v[2][2][RT];                     // [step parity][point half][channel]
+  __shared__ int pm_p[2][2][RT];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -680,6 +688,27 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
   const __amdgpu_buffer_rsrc_t rw = pf_rsrc(p.W + (int64_t)b * p.Co * p.Ci, p.w_extent);
   const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + b * p.xsb + n * p.xsn, p.x_extent);
   const __amdgpu_buffer_rsrc_t rgam = pf_rsrc(p.gamma + (int64_t)b * p.Co, (uint32_t)p.Co * 4u);
+
+  // W tiles: rows t/4 (+64), 16-byte group t%4 of every 32-wide k block; a row whose gamma is
+  // negative gets the sign bit of every element flipped (exact), so that every channel looks for a maximum
+  const int wr = t >> 2, wg = (t & 3) * 8;
+  uint4 wq[SUB][H];
+  uint32_t gq[H];                        // the rows' gamma, raw bits: looked at only when the tile is parked
+  auto load_w = [&](int ct) {
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+      const int row = ct * RT + wr + 64 * h;
+      gq[h] = __builtin_amdgcn_raw_buffer_load_b32(rgam, (int)(row < p.Co ? (uint32_t)row * 4u : PF_OOB), 0, 0);
+#pragma unroll
+      for (int s = 0; s < SUB; ++s) {
+        const int k = s * 32 + wg;
+        const bool ok = row < p.Co && k + 8 <= p.Ci;
+        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(ok ? ((uint32_t)row * (uint32_t)p.Ci + (uint32_t)k) * 2u : PF_OOB), 0, 0);
+        wq[s][h] = make_uint4(v.x, v.y, v.z, v.w);
+      }
+    }
+  };
+  load_w(0);
 
   {  // X tile, transposed in registers into [point][ci]
     const int kq = t % 8, ng = t / 8;
@@ -706,30 +735,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
       o[3] = make_uint2((b0 >> 16) | (b1 & 0xffff0000u), (b2 >> 16) | (b3 & 0xffff0000u));
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<uint2*>(Xs + (ng * 4 + i) * PITCH + s * 64 + kq * 8) = o[i];
+        *reinterpret_cast<uint2*>(smem + (ng * 4 + i) * PITCH + s * 64 + kq * 8) = o[i];
     }
   }
-
-  // W tiles: rows t/4 and t/4+64, 16-byte group t%4 of every 32-wide k block; a row whose gamma is
-  // negative gets the sign bit of every element flipped (exact), so that every channel looks for a maximum
-  const int wr = t >> 2, wg = (t & 3) * 8;
-  uint4 wq[SUB][2];
-  uint32_t gq[2];                        // the rows' gamma, raw bits: looked at only when the tile is parked
-  auto load_w = [&](int ct) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int row = ct * 128 + wr + 64 * h;
-      gq[h] = __builtin_amdgcn_raw_buffer_load_b32(rgam, (int)(row < p.Co ? (uint32_t)row * 4u : PF_OOB), 0, 0);
-#pragma unroll
-      for (int s = 0; s < SUB; ++s) {
-        const int k = s * 32 + wg;
-        const bool ok = row < p.Co && k + 8 <= p.Ci;
-        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(ok ? ((uint32_t)row * (uint32_t)p.Ci + (uint32_t)k) * 2u : PF_OOB), 0, 0);
-        wq[s][h] = make_uint4(v.x, v.y, v.z, v.w);
-      }
-    }
-  };
-  load_w(0);
 
   const int r = lane & 31, gsel = lane >> 5;
   const int tiles = gridDim.x;
@@ -737,19 +745,19 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
   int* pidx = p.pidx + ((int64_t)bz * tiles + bx) * p.Co;
   const int lim = p.L - l0;                              // points of this slice that exist (>= 1)
   auto publish = [&](int ct) {                           // step ct's per-channel result, both point halves merged
-    if (t < 128 && ct * 128 + t < p.Co) {
+    if (t < RT && ct * RT + t < p.Co) {
       const int pb = ct & 1;
       const float v0 = pm_v[pb][0][t], v1 = pm_v[pb][1][t];
       const bool hi = v1 > v0;                           // a tie goes to the lower points
-      pmax[ct * 128 + t] = hi ? v1 : v0;
-      pidx[ct * 128 + t] = l0 + (hi ? pm_p[pb][1][t] : pm_p[pb][0][t]);
+      pmax[ct * RT + t] = hi ? v1 : v0;
+      pidx[ct * RT + t] = l0 + (hi ? pm_p[pb][1][t] : pm_p[pb][0][t]);
     }
   };
   auto park_w = [&](unsigned char* dst) {                // the W tile in registers -> LDS, sign-folded
 #pragma unroll
     for (int s = 0; s < SUB; ++s)
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
+      for (int h = 0; h < H; ++h) {
         const uint4 w = wq[s][h];
         const uint32_t flip = __uint_as_float(gq[h]) < 0.f ? 0x80008000u : 0u;
         *reinterpret_cast<uint4*>(dst + (wr + 64 * h) * PITCH + (s * 32 + wg) * 2) =
@@ -758,64 +766,65 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
   };
 
   // The X operand of this wavefront never changes: its matrix-instruction fragments move from LDS
-  // into registers once, and the X tile's LDS becomes the second W buffer.
-  park_w(Ws);
+  // into registers once, and the X tile's LDS becomes the two W buffers.
   __syncthreads();
-  load_w(1);
   bf16x8_t xf[2][KT / 16];
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int s = 0; s < KT / 16; ++s)
-      xf[j][s] = *reinterpret_cast<const bf16x8_t*>(Xs + (wn * 64 + j * 32 + r) * PITCH + (2 * s + gsel) * 16);
+      xf[j][s] = *reinterpret_cast<const bf16x8_t*>(smem + (wn * 64 + j * 32 + r) * PITCH + (2 * s + gsel) * 16);
   {  // this slice's part of sum_l x: thread (ci, half) adds 64 points in order
     const int ci = t & 127, half = t >> 7;
     if (ci < p.Ci) {
       float sx = 0.f;
-      const unsigned char* col = Xs + (half * 64) * PITCH + ci * 2;
+      const unsigned char* col = smem + (half * 64) * PITCH + ci * 2;
 #pragma unroll 8
       for (int q = 0; q < 64; ++q) sx += bf16_to_f32(*reinterpret_cast<const bf16_raw*>(col + q * PITCH));
       p.SXpart[(((int64_t)bz * tiles + bx) * 2 + half) * p.Ci + ci] = sx;
     }
   }
   __syncthreads();                       // the X tile is dead
+  park_w(smem);
+  load_w(1);
+  __syncthreads();
 
   for (int ct = 0; ct < p.tiles_co; ++ct) {
-    unsigned char* cur = (ct & 1) ? Xs : Ws;
-    park_w((ct & 1) ? Ws : Xs);          // tile ct+1; that buffer was last read in step ct-1
+    const unsigned char* cur = smem + (ct & 1) * WTILE;
+    park_w(smem + ((ct + 1) & 1) * WTILE);   // tile ct+1; that buffer was last read in step ct-1
     load_w(ct + 2);                      // past the last tile: rows >= Co, zeros, no traffic
     if (ct > 0) publish(ct - 1);
 
-    f32x16_t acc[2][2];
+    f32x16_t acc[H][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < H; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 #pragma unroll
     for (int s = 0; s < KT / 16; ++s) {
-      bf16x8_t a[2];
+      bf16x8_t a[H];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        a[i] = *reinterpret_cast<const bf16x8_t*>(cur + (wm * 64 + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
+      for (int i = 0; i < H; ++i)
+        a[i] = *reinterpret_cast<const bf16x8_t*>(cur + (wm * (RT / 2) + i * 32 + r) * PITCH + (2 * s + gsel) * 16);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < H; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[j][s], a[i], acc[i][j], 0, 0, 0);
     }
-    // lane = channel wm*64 + i*32 + (lane & 31); its 32 points wn*64 + j*32 + 8q + 4(lane>>5) + e in rising order
+    // lane = channel wm*(RT/2) + i*32 + (lane & 31); its 32 points wn*64 + j*32 + 8q + 4(lane>>5) + e in rising order.
     // Two passes per channel: the maximum of the lane's 32 values (no index carried), then the
     // first position that holds it, walking the positions downwards so the lowest one is kept.
-    float bv[2];
-    int bp[2];
+    float bv[H];
+    int bp[H];
     const int pt0 = wn * 64 + 4 * gsel;
     if (lim < 128) {                       // the last slice: points past L do not take part
       int room = lim - pt0;                // opaque to the optimizer: 64 loop-invariant lane masks
       asm volatile("" : "+v"(room));       // would otherwise be kept (and spilled) across the loop
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < H; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -823,7 +832,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
             if (j * 32 + 8 * (v >> 2) + (v & 3) >= room) acc[i][j][v] = -INFINITY;
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < H; ++i) {
       float m[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q)
@@ -832,7 +841,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
       bv[i] = fmax3(fmax3(m[0], m[1], m[2]), fmax3(m[3], m[4], m[5]), fmax3(m[6], m[7], -INFINITY));
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < H; ++i) {
       int rel = 0;
 #pragma unroll
       for (int j = 1; j >= 0; --j)
@@ -842,13 +851,13 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void fbp_main_kernel(FbpArgs p) { 
       bp[i] = pt0 + rel;
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {        // the two lane halves hold interleaved groups of four points
+    for (int i = 0; i < H; ++i) {        // the two lane halves hold interleaved groups of four points
       const float ov = __shfl_xor(bv[i], 32, 64);
       const int op = __shfl_xor(bp[i], 32, 64);
       if (ov > bv[i] || (ov == bv[i] && op < bp[i])) { bv[i] = ov; bp[i] = op; }
       if (lane < 32) {
-        pm_v[ct & 1][wn][wm * 64 + i * 32 + lane] = bv[i];
-        pm_p[ct & 1][wn][wm * 64 + i * 32 + lane] = bp[i];
+        pm_v[ct & 1][wn][wm * (RT / 2) + i * 32 + lane] = bv[i];
+        pm_p[ct & 1][wn][wm * (RT / 2) + i * 32 + lane] = bp[i];
       }
     }
     __syncthreads();                     // tile ct+1 is in LDS, tile ct is free, step ct's maxima are published next
@@ -1093,7 +1102,7 @@ int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   a.running_mean = running_mean; a.running_var = running_var; a.save_mean = save_mean; a.save_invstd = save_invstd;
   a.V = (bf16_raw*)V; a.idx = idx; a.zhit = zhit;
   a.xsb = xs[0]; a.xsn = xs[1]; a.xsc = xs[2]; a.vsb = vs[0]; a.vsn = vs[1]; a.vsc = vs[2];
-  a.B = B; a.Nb = Nb; a.Ci = Ci; a.Co = Co; a.L = L; a.act = act; a.tiles_co = (Co + 127) / 128;
+  a.B = B; a.Nb = Nb; a.Ci = Ci; a.Co = Co; a.L = L; a.act = act; a.tiles_co = (Co + FBP_RT - 1) / FBP_RT;
   a.slope = act_slope; a.eps = eps; a.momentum = momentum;
   a.XX = saved_moments ? saved_moments : (float*)(ws + lay.moments);
   a.SX = a.XX + (size_t)B * Ci * Ci;
@@ -1104,8 +1113,8 @@ int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, st);
   if (rc != HFTA_OK) return rc;
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
-  if (Ci <= 64) hipLaunchKernelGGL(fbp_main_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
-  else hipLaunchKernelGGL(fbp_main_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);
+  if (Ci <= 64) hipLaunchKernelGGL((fbp_main_kernel<64, FBP_RT>), grid, dim3(GEMM_THREADS), 0, st, a);
+  else hipLaunchKernelGGL((fbp_main_kernel<128, FBP_RT>), grid, dim3(GEMM_THREADS), 0, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   hipLaunchKernelGGL(cbp_sx_kernel, dim3((unsigned)((Ci + 15) / 16), (unsigned)B), dim3(1024), 0, st, a.SXpart, a.SX, Ci,
                      Nb * (int)grid.x * 2);
