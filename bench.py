@@ -34,7 +34,7 @@ class Tracer:
     sequence) are bracketed by HIP events on the stream they launch on (torch's current stream)."""
 
     SINGLE_KERNEL = ("conv1x1_fwd", "conv1x1_bwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
-                     "adam_step_multi", "linear_fwd", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
+                     "adam_step_multi", "linear_fwd", "linear_fwd_ws", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
                      "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd",
                      "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_fwd",
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
@@ -96,7 +96,9 @@ def kernel_label(name, a):
         if dt == 1 and big_gemm(B * Nb, Co, L, Ci):
             return "gemm_big_kernel(fwd)"
         return "gemm_pf_kernel(fwd)" if dt == 1 else "gemm_kernel(fwd)"
-    if name == "linear_fwd":
+    if name == "linear_fwd_ws" and a[1] <= 64:
+        return ("gemm_pf_kernel" if a[4] == 1 else "gemm_kernel") + "(fwd, split)+splitk_bias_act_kernel"
+    if name in ("linear_fwd", "linear_fwd_ws"):
         if a[4] == 1 and big_gemm(a[0], a[1], a[3], a[2]):
             return "gemm_big_kernel(fwd)"
         return "gemm_pf_kernel(fwd)" if a[4] == 1 else "gemm_kernel(fwd)"
@@ -163,7 +165,7 @@ def big_gemm_split(G, M, N, K, S=1):
 
 
 def algorithmic_flops(name, a):
-    if name in ("linear_fwd", "linear_bwd"):
+    if name in ("linear_fwd", "linear_fwd_ws", "linear_bwd"):
         B, M, Fx, Fy = a[:4]
         if name == "linear_bwd" and a[8] is None and a[9] is None:
             return 0.0
@@ -204,7 +206,7 @@ def algorithmic_bytes(name, a):
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         return (B * Nb * (Ci + Co) * L + B * Co * (Ci + 1)) * _es(dt)
-    if name == "linear_fwd":
+    if name in ("linear_fwd", "linear_fwd_ws"):
         B, M, Fx, Fy, dt = a[:5]
         return B * (M * Fx + Fx * Fy + Fy + M * Fy) * _es(dt)
     if name == "conv1x1_bwd":

@@ -80,6 +80,17 @@ int hfta_linear_fwd(int B, int M, int Fx, int Fy, int dtype,
                     const void* X, const void* W, const void* bias, void* Y,
                     int act, float act_slope, void* stream);
 
+/* The same operation with a workspace.  With few rows per model (M <= 64: a fully connected head
+ * fed by one pooled vector per sample) the reduction over Fx is cut into pieces that run on
+ * different compute units; fp32 partial products [split][B][M][Fy] pass through the workspace and a
+ * second launch adds them in a fixed order, then bias and act.  Results equal hfta_linear_fwd's up
+ * to fp32 summation order.  hfta_linear_fwd_workspace_bytes is 0 where no split is used (then the
+ * call is hfta_linear_fwd); EWORKSPACE below that size. */
+size_t hfta_linear_fwd_workspace_bytes(int B, int M, int Fx, int Fy, int dtype);
+int hfta_linear_fwd_ws(int B, int M, int Fx, int Fy, int dtype,
+                       const void* X, const void* W, const void* bias, void* Y,
+                       int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
+
 /* Backward of hfta_linear_fwd with act = NONE (apply hfta_act_bwd first otherwise).
  *   dX[b] = dY[b] W[b]^T   (storage dtype; NULL = skip)
  *   dW[b] = X[b]^T dY[b]   (fp32 [B][Fx][Fy]; NULL = skip)

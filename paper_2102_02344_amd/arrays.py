@@ -225,7 +225,8 @@ class FusedPointNetCls(ParamArena):
         for i in range(self.nconv):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nfc):
-            ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt))
+            ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt),
+                     hb.linear_fwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt))
         if not self.fused_tail:
             self.fused_tail_ws = 0
         ws = max(ws, self.fused_tail_ws)
@@ -297,7 +298,7 @@ class FusedPointNetCls(ParamArena):
             k = f"fc{i}"
             last = i == self.nfc - 1
             if last or s.fc_bn:
-                hb.linear_fwd(B, Nb, fx, fy, dt, h, self.w(k + ".w"), self.w(k + ".b"), self.fz[i])
+                hb.linear_fwd_ws(B, Nb, fx, fy, dt, h, self.w(k + ".w"), self.w(k + ".b"), self.fz[i], workspace=self.ws)
                 P("linear_fwd", layer=k, x=h, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.fz[i], act=0)
                 if not last:
                     ls = (Nb * fy, fy, 1, 1)
@@ -308,7 +309,8 @@ class FusedPointNetCls(ParamArena):
                       b=self.master(k + ".bn.b"), y=self.fh[i], mean=self.saved[k + ".bn.mean"],
                       invstd=self.saved[k + ".bn.invstd"])
             else:
-                hb.linear_fwd(B, Nb, fx, fy, dt, h, self.w(k + ".w"), self.w(k + ".b"), self.fh[i], hb.ACT_RELU)
+                hb.linear_fwd_ws(B, Nb, fx, fy, dt, h, self.w(k + ".w"), self.w(k + ".b"), self.fh[i], hb.ACT_RELU,
+                                 workspace=self.ws)
                 P("linear_fwd", layer=k, x=h, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.fh[i], act=1)
             if last:
                 h = self.fz[i]
@@ -835,7 +837,8 @@ class FusedPointNetSeg(ParamArena):
         cmax = max(max(spec.conv[1:]), max(H[1:]))
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(3)]
         self.loss = torch.empty(B, **f32)
-        ws = max(4, hb.softmax_xent_points_workspace_bytes(B, Nb, L), hb.linear_bwd_workspace_bytes(B, Nb, Cg, H[1], self.dt))
+        ws = max(4, hb.softmax_xent_points_workspace_bytes(B, Nb, L), hb.linear_bwd_workspace_bytes(B, Nb, Cg, H[1], self.dt),
+                 hb.linear_fwd_workspace_bytes(B, Nb, Cg, H[1], self.dt))
         for i in range(self.nconv):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nh):
@@ -871,7 +874,7 @@ class FusedPointNetSeg(ParamArena):
         hb.maxpool_points(B, Nb, C4, L, dt, x, cst, self.gfeat, self.pool_idx, self.gvs)
         P("maxpool_points", x=xv, v=self.gfeat[:, :, :C4], idx=self.pool_idx[:, :, :C4])
         # ---- head: first layer = per-point block over the concatenation + once-per-sample block
-        hb.linear_fwd(B, Nb, Cg, H[1], dt, self.gfeat, self.w("head0.wg"), None, self.hg)
+        hb.linear_fwd_ws(B, Nb, Cg, H[1], dt, self.gfeat, self.w("head0.wg"), None, self.hg, workspace=self.ws)
         P("linear_fwd", layer="head0.wg", x=self.gfeat, w=self.w("head0.wg"), y=self.hg)
         h, hs, hv, ci = self.cat, cst, self.cat, Cp
         for i in range(self.nh):

@@ -42,6 +42,8 @@ _SIGS = {
     "hfta_status_string": (C.c_char_p, [_i]),
     "hfta_version": (_i, []),
     "hfta_linear_fwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _i, _f, _p]),
+    "hfta_linear_fwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
+    "hfta_linear_fwd_ws": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _i, _f, _p, _sz, _p]),
     "hfta_linear_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
     "hfta_linear_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_conv1x1_fwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _s4, _i, _f, _p]),
@@ -150,6 +152,16 @@ def _ws(workspace):
 def linear_fwd(B, M, Fx, Fy, dtype, X, W, bias, Y, act=ACT_NONE, act_slope=0.0, stream=None):
     _check(_lib.hfta_linear_fwd(B, M, Fx, Fy, dtype, _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), act, act_slope,
                                 _stream(stream)), "hfta_linear_fwd")
+
+
+def linear_fwd_workspace_bytes(B, M, Fx, Fy, dtype) -> int:
+    return _lib.hfta_linear_fwd_workspace_bytes(B, M, Fx, Fy, dtype)
+
+
+def linear_fwd_ws(B, M, Fx, Fy, dtype, X, W, bias, Y, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_linear_fwd_ws(B, M, Fx, Fy, dtype, _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), act, act_slope,
+                                   wp, wb, _stream(stream)), "hfta_linear_fwd_ws")
 
 
 def linear_bwd_workspace_bytes(B, M, Fx, Fy, dtype) -> int:

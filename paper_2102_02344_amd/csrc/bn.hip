@@ -130,30 +130,51 @@ __global__ __launch_bounds__(1024) void bn_fwd_conv_reg_kernel(BnFwdArgs p) {
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void bn_fwd_linear_kernel(BnFwdArgs p) {
-  const int c = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
-  if (c >= p.C) return;
-  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c;
-  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c;
+// Linear layout [.., Nb, C] (channel stride 1, the fully connected head): a workgroup owns 64
+// channels x 16 sample lanes, so the loads of a column are spread over lanes instead of walking one
+// after the other through the memory latency; per-lane partial sums meet in LDS in a fixed order.
+constexpr int BNL_C = 64, BNL_N = 16;
+
+__device__ __forceinline__ float bnl_reduce(float v, float (*red)[BNL_C], int tx, int ty) {
+  __syncthreads();                       // the previous reduction's readers are done
+  red[ty][tx] = v;
+  __syncthreads();
   float s = 0.f;
-  for (int n = 0; n < p.Nb; ++n) s += Elem<T>::load(x + n * p.xsn);
+#pragma unroll
+  for (int j = 0; j < BNL_N; ++j) s += red[j][tx];
+  return s;
+}
+
+template <typename T>
+__global__ __launch_bounds__(BNL_C * BNL_N) void bn_fwd_linear_kernel(BnFwdArgs p) {
+  __shared__ float red[BNL_N][BNL_C];
+  const int tx = threadIdx.x % BNL_C, ty = threadIdx.x / BNL_C;
+  const int c = blockIdx.x * BNL_C + tx, b = blockIdx.y;
+  const bool live = c < p.C;
+  const int cc = live ? c : p.C - 1;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + cc;
+  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + cc;
+  float s = 0.f;
+  for (int n = ty; n < p.Nb; n += BNL_N) s += Elem<T>::load(x + n * p.xsn);
   const float m = (float)p.Nb;
-  const float mean = s / m;
+  const float mean = bnl_reduce(s, red, tx, ty) / m;
   float q = 0.f;
-  for (int n = 0; n < p.Nb; ++n) { const float d = Elem<T>::load(x + n * p.xsn) - mean; q = fmaf(d, d, q); }
-  const float var = q / m;
+  for (int n = ty; n < p.Nb; n += BNL_N) { const float d = Elem<T>::load(x + n * p.xsn) - mean; q = fmaf(d, d, q); }
+  const float var = bnl_reduce(q, red, tx, ty) / m;
   const float invstd = 1.0f / sqrtf(var + p.eps);
-  const int k = b * p.C + c;
+  const int k = b * p.C + cc;
   const float g = p.gamma[k], bt = p.beta[k];
-  p.save_mean[k] = mean;
-  p.save_invstd[k] = invstd;
-  if (p.running_mean) {
-    const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
-    p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
-    p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
+  if (live && ty == 0) {
+    p.save_mean[k] = mean;
+    p.save_invstd[k] = invstd;
+    if (p.running_mean) {
+      const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
+      p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
+      p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
+    }
   }
-  for (int n = 0; n < p.Nb; ++n) {
+  if (!live) return;
+  for (int n = ty; n < p.Nb; n += BNL_N) {
     const float v = Elem<T>::load(x + n * p.xsn);
     Elem<T>::store(y + n * p.ysn, apply_act(fmaf(g, (v - mean) * invstd, bt), p.act, p.slope));
   }
@@ -281,33 +302,43 @@ __global__ __launch_bounds__(1024) void bn_bwd_conv_reg_kernel(BnBwdArgs p) {
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void bn_bwd_linear_kernel(BnBwdArgs p) {
-  const int c = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
-  if (c >= p.C) return;
-  const int k = b * p.C + c;
-  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c;
-  const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + c;
-  T* dx = reinterpret_cast<T*>(p.dX) + b * p.dxsb + c;
+__global__ __launch_bounds__(BNL_C * BNL_N) void bn_bwd_linear_kernel(BnBwdArgs p) {
+  __shared__ float red[BNL_N][BNL_C];
+  const int tx = threadIdx.x % BNL_C, ty = threadIdx.x / BNL_C;
+  const int c = blockIdx.x * BNL_C + tx, b = blockIdx.y;
+  const bool live = c < p.C;
+  const int cc = live ? c : p.C - 1;
+  const int k = b * p.C + cc;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + cc;
+  const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + cc;
+  T* dx = reinterpret_cast<T*>(p.dX) + b * p.dxsb + cc;
   const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
   float s1 = 0.f, s2 = 0.f;
-  for (int n = 0; n < p.Nb; ++n) {
+  for (int n = ty; n < p.Nb; n += BNL_N) {
     const float xh = (Elem<T>::load(x + n * p.xsn) - mean) * invstd;
     const float gr = Elem<T>::load(dy + n * p.dysn) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
     s1 += gr;
     s2 = fmaf(gr, xh, s2);
   }
-  p.dbeta[k] = s1;
-  p.dgamma[k] = s2;
+  s1 = bnl_reduce(s1, red, tx, ty);
+  s2 = bnl_reduce(s2, red, tx, ty);
+  if (live && ty == 0) {
+    p.dbeta[k] = s1;
+    p.dgamma[k] = s2;
+  }
   const float m = (float)p.Nb, mb = s1 / m, mg = s2 / m, sc = g * invstd;
   float s3 = 0.f;
-  for (int n = 0; n < p.Nb; ++n) {
+  for (int n = ty; n < p.Nb; n += BNL_N) {
     const float xh = (Elem<T>::load(x + n * p.xsn) - mean) * invstd;
     const float gr = Elem<T>::load(dy + n * p.dysn) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
     const T o = Elem<T>::from_f32(sc * (gr - mb - xh * mg));
-    dx[n * p.dxsn] = o;
+    if (live) dx[n * p.dxsn] = o;
     s3 += Elem<T>::to_f32(o);
   }
-  if (p.dx_sum) p.dx_sum[k] = s3;
+  if (p.dx_sum) {                        // uniform over the grid
+    s3 = bnl_reduce(s3, red, tx, ty);
+    if (live && ty == 0) p.dx_sum[k] = s3;
+  }
 }
 
 bool vec_ok(const void* p, const int64_t* s, int L, int dtype) {
@@ -351,9 +382,9 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
               xs[0], xs[1], xs[2], ys[0], ys[1], ys[2], Nb, C, L, act, eps, momentum, act_slope};
   hipStream_t st = as_stream(stream);
   if (kx == 2) {
-    dim3 grid((unsigned)((C + 255) / 256), (unsigned)B);
-    if (dtype == HFTA_BF16) hipLaunchKernelGGL(bn_fwd_linear_kernel<bf16_raw>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(bn_fwd_linear_kernel<float>, grid, dim3(256), 0, st, a);
+    dim3 grid((unsigned)((C + BNL_C - 1) / BNL_C), (unsigned)B);
+    if (dtype == HFTA_BF16) hipLaunchKernelGGL(bn_fwd_linear_kernel<bf16_raw>, grid, dim3(BNL_C * BNL_N), 0, st, a);
+    else hipLaunchKernelGGL(bn_fwd_linear_kernel<float>, grid, dim3(BNL_C * BNL_N), 0, st, a);
     return launch_status();
   }
   dim3 grid((unsigned)C, (unsigned)B);
@@ -390,9 +421,9 @@ int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
               xs[0], xs[1], xs[2], dys[0], dys[1], dys[2], dxs[0], dxs[1], dxs[2], Nb, C, L, act, act_slope};
   hipStream_t st = as_stream(stream);
   if (kx == 2) {
-    dim3 grid((unsigned)((C + 255) / 256), (unsigned)B);
-    if (dtype == HFTA_BF16) hipLaunchKernelGGL(bn_bwd_linear_kernel<bf16_raw>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(bn_bwd_linear_kernel<float>, grid, dim3(256), 0, st, a);
+    dim3 grid((unsigned)((C + BNL_C - 1) / BNL_C), (unsigned)B);
+    if (dtype == HFTA_BF16) hipLaunchKernelGGL(bn_bwd_linear_kernel<bf16_raw>, grid, dim3(BNL_C * BNL_N), 0, st, a);
+    else hipLaunchKernelGGL(bn_bwd_linear_kernel<float>, grid, dim3(BNL_C * BNL_N), 0, st, a);
     return launch_status();
   }
   dim3 grid((unsigned)C, (unsigned)B);

@@ -45,6 +45,7 @@ struct GemmDesc {
   bool out_f32;
   int splits;                      // > 1: fp32 partials [split][G0*G1][M][N] go to `partial`
   float* partial;
+  bool keep_partials;              // splits > 1: leave the partials unsummed (the caller's epilogue adds them); C unused
   // C's columns in segments of c_seg (0 = one contiguous row): column n lives at
   // (n / c_seg) * c_seg_stride + n % c_seg past the row start (an [N][C][HW] image tensor seen as [C][N*HW])
   int c_seg;

@@ -188,7 +188,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
       b.total_tiles = d.S * b.tiles_per_seg;
       dim3 grid((unsigned)(b.tiles_m * b.tiles_n), 1, (unsigned)(G * splits));
       const int rc = gemm_big_launch(d, b, v16 || !(d.a_kc || d.b_kc), grid, st);
-      if (rc == HFTA_OK && splits > 1) return reduce_partials(d, G, splits, st);
+      if (rc == HFTA_OK && splits > 1 && !d.keep_partials) return reduce_partials(d, G, splits, st);
       if (rc != HFTA_EUNSUPPORTED) return rc;
     }
   }
@@ -205,7 +205,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
     rc = d.dtype == HFTA_BF16 ? launch_layout<bf16_raw>(d, a, grid, st) : launch_layout<float>(d, a, grid, st);
   }
   if (rc != HFTA_OK) return rc;
-  if (splits > 1) return reduce_partials(d, G, splits, st);
+  if (splits > 1 && !d.keep_partials) return reduce_partials(d, G, splits, st);
   return HFTA_OK;
 }
 

@@ -160,12 +160,44 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const T* __restrict__ dY, f
 
 bool fits_i32(int64_t v) { return v > 0 && v <= 0x7fffffffLL; }
 
+// Epilogue of the split forward of a Linear with few rows: Y = act(sum_s partial[s] + bias), the
+// splits added in a fixed order; one thread per output element, consecutive threads on consecutive columns.
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_bias_act_kernel(const float* __restrict__ partial, T* __restrict__ Y,
+                                                              const T* __restrict__ bias, int64_t count, int MN, int N,
+                                                              int splits, int act, float slope) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float s = 0.f;
+#pragma unroll 4
+  for (int k = 0; k < splits; ++k) s += partial[(int64_t)k * count + i];
+  if (bias) {
+    const int64_t b = i / MN;
+    s += Elem<T>::load(bias + b * N + (i - b * MN) % N);
+  }
+  Elem<T>::store(Y + i, apply_act(s, act, slope));
+}
+
+// Few rows, long reduction: one 128-row tile per model and column block leaves most of the chip
+// idle and walks K in sequence; the reduction is cut into pieces of at least two k-tiles until
+// about 256 workgroups exist.
+int linear_fwd_splits(int B, int M, int Fx, int Fy, int dtype) {
+  if (M > 64) return 1;
+  const int bk = dtype == HFTA_BF16 ? GemmT<bf16_raw>::BK : GemmT<float>::BK;
+  const int64_t tiles = (int64_t)((Fy + GEMM_BN - 1) / GEMM_BN) * B;
+  const int tt = (Fx + bk - 1) / bk;
+  int64_t want = (256 + tiles - 1) / tiles;
+  if (want > tt / 2) want = tt / 2;
+  if (want > 64) want = 64;
+  return want < 2 ? 1 : (int)want;
+}
+
 GemmDesc base_desc(int dtype) {
   GemmDesc d{};
   d.S = 1; d.G0 = 1; d.G1 = 1;
   d.act = HFTA_ACT_NONE; d.slope = 0.f;
   d.dtype = dtype; d.out_f32 = false; d.splits = 1; d.partial = nullptr;
-  d.bias = nullptr; d.bias_mode = 0;
+  d.bias = nullptr; d.bias_mode = 0; d.keep_partials = false;
   return d;
 }
 
@@ -210,6 +242,42 @@ int hfta_linear_fwd(int B, int M, int Fx, int Fy, int dtype, const void* X, cons
   d.bias = bias; d.bias_mode = 2; d.bias_g0 = Fy;
   d.act = act; d.slope = act_slope;
   return gemm_launch(d, as_stream(stream));
+}
+
+size_t hfta_linear_fwd_workspace_bytes(int B, int M, int Fx, int Fy, int dtype) {
+  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !valid_dtype(dtype)) return 0;
+  const int splits = linear_fwd_splits(B, M, Fx, Fy, dtype);
+  return splits > 1 ? (size_t)splits * B * M * Fy * sizeof(float) : 0;
+}
+
+int hfta_linear_fwd_ws(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* W, const void* bias,
+                       void* Y, int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !X || !W || !Y || !valid_dtype(dtype) || !valid_act(act))
+    return HFTA_EINVAL;
+  const int splits = linear_fwd_splits(B, M, Fx, Fy, dtype);
+  if (splits <= 1) return hfta_linear_fwd(B, M, Fx, Fy, dtype, X, W, bias, Y, act, act_slope, stream);
+  if (!fits_i32((int64_t)M * Fx) || !fits_i32((int64_t)M * Fy) || !fits_i32((int64_t)Fx * Fy)) return HFTA_EINVAL;
+  const size_t need = (size_t)splits * B * M * Fy * sizeof(float);
+  if (!workspace || ws_bytes < need) return HFTA_EWORKSPACE;
+  GemmDesc d = base_desc(dtype);
+  d.A = X; d.Bm = W; d.C = nullptr;
+  d.M = M; d.N = Fy; d.K = Fx; d.G0 = B;
+  d.a_kc = true; d.a_ld = Fx; d.a_g0 = (int64_t)M * Fx;
+  d.b_kc = false; d.b_ld = Fy; d.b_g0 = (int64_t)Fx * Fy;
+  d.c_ld = Fy; d.c_g0 = (int64_t)M * Fy;
+  d.out_f32 = true; d.splits = splits; d.partial = reinterpret_cast<float*>(workspace); d.keep_partials = true;
+  hipStream_t st = as_stream(stream);
+  const int rc = gemm_launch(d, st);
+  if (rc != HFTA_OK) return rc;
+  const int64_t count = (int64_t)B * M * Fy;
+  dim3 grid((unsigned)((count + 255) / 256));
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL(splitk_bias_act_kernel<bf16_raw>, grid, dim3(256), 0, st, d.partial, (bf16_raw*)Y,
+                       (const bf16_raw*)bias, count, M * Fy, Fy, splits, act, act_slope);
+  else
+    hipLaunchKernelGGL(splitk_bias_act_kernel<float>, grid, dim3(256), 0, st, d.partial, (float*)Y,
+                       (const float*)bias, count, M * Fy, Fy, splits, act, act_slope);
+  return launch_status();
 }
 
 size_t hfta_linear_bwd_workspace_bytes(int B, int M, int Fx, int Fy, int dtype) {

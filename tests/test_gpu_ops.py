@@ -79,6 +79,35 @@ def test_linear_identity_and_B1(hb):
     assert torch.equal(Y1[0], Y[0])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,M,Fx,Fy,act", [(8, 32, 1024, 512, 0), (3, 32, 512, 256, 1), (2, 7, 256, 40, 0),
+                                           (2, 64, 200, 130, 3), (2, 65, 256, 128, 0), (2, 4, 16, 16, 1)])
+def test_linear_fwd_with_workspace(hb, dtype, B, M, Fx, Fy, act):
+    """Few rows per model: the reduction is split over workgroups, the partial products are added in
+    a fixed order with bias and activation; otherwise (M > 64, short K) the call is the plain forward."""
+    print(f"linear_fwd_ws {dtype} B={B} M={M} Fx={Fx} Fy={Fy} act={act}", flush=True)
+    x = hi.normal(41, (B, M, Fx), dtype)
+    w = hi.normal(42, (B, Fx, Fy), dtype, 1.0 / np.sqrt(Fx))
+    b = hi.normal(43, (B, Fy), dtype)
+    X, W, Bi = dev(x, dtype), dev(w, dtype), dev(b, dtype)
+    nws = hb.linear_fwd_workspace_bytes(B, M, Fx, Fy, DT[dtype])
+    assert (nws > 0) == (M <= 64 and Fx >= (128 if dtype == "bf16" else 64))
+    ws = torch.empty(max(nws, 4), dtype=torch.uint8, device="cuda")
+    Y = empty((B, M, Fy), dtype)
+    hb.linear_fwd_ws(B, M, Fx, Fy, DT[dtype], X, W, Bi, Y, act, 0.1, ws)
+    ref = oops.act_fwd(oa.linear_fwd(B, x, w, b), act, 0.1)
+    check(host(Y), ref, TOL[dtype], "Y")
+    Y2 = empty((B, M, Fy), dtype)
+    hb.linear_fwd_ws(B, M, Fx, Fy, DT[dtype], X, W, None, Y2, act, 0.1, ws)
+    check(host(Y2), oops.act_fwd(oa.linear_fwd(B, x, w, None), act, 0.1), TOL[dtype], "Y without bias")
+    Y3 = empty((B, M, Fy), dtype)
+    hb.linear_fwd_ws(B, M, Fx, Fy, DT[dtype], X, W, Bi, Y3, act, 0.1, ws)
+    assert torch.equal(Y, Y3)
+    if nws > 0:
+        with pytest.raises(RuntimeError):
+            hb.linear_fwd_ws(B, M, Fx, Fy, DT[dtype], X, W, Bi, Y3, act, 0.1, None)
+
+
 # ------------------------------------------------------------------ conv1x1
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Nb,Ci,Co,L", [(3, 2, 70, 150, 300), (2, 3, 3, 64, 250), (2, 2, 128, 40, 129),
@@ -217,8 +246,9 @@ def test_bn_conv_layout(hb, dtype, B, Nb, C, L, act):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_bn_linear_layout_and_independence(hb, dtype):
-    B, Nb, C = 3, 32, 300
+@pytest.mark.parametrize("Nb", [32, 5, 64, 100])      # up to 64 samples: the column-in-registers kernels
+def test_bn_linear_layout_and_independence(hb, dtype, Nb):
+    B, C = 3, 300
     x = hi.snap(hi.normal(31, (B, Nb, C)) * 1.5 - 0.7, dtype)
     g, bt = (hi.normal(32, (B, C)) * 0.5 + 1.0), hi.normal(33, (B, C)) * 0.3
     dy = hi.normal(34, (B, Nb, C), dtype)
