@@ -171,6 +171,68 @@ def pointnet_cls_inputs(spec: PointNetClsSpec, seed: Optional[int] = None) -> Di
 
 
 # --------------------------------------------------------------------------
+# PointNet-cls with the input / feature transform sub-networks
+# --------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class PointNetTSpec:
+    """A PointNet-cls array whose models carry transform sub-networks: per-point layers
+    k -> tnet_conv..., max over points, Linear layers tnet_fc... -> k*k; k = 3 on the coordinates
+    (input transform), k = cls.conv[1] on the first layer's output (feature transform)."""
+    cls: PointNetClsSpec
+    tnet_conv: Tuple[int, ...] = (64, 128, 1024)
+    tnet_fc: Tuple[int, ...] = (512, 256)
+    input_transform: bool = True
+    feature_transform: bool = True
+
+
+def tnet_sizes(tspec: PointNetTSpec) -> List[int]:
+    return ([3] if tspec.input_transform else []) + ([tspec.cls.conv[1]] if tspec.feature_transform else [])
+
+
+def pointnet_t_param_shapes(tspec: PointNetTSpec) -> List[Tuple[str, Tuple[int, ...]]]:
+    out = list(pointnet_cls_param_shapes(tspec.cls))
+    for k in tnet_sizes(tspec):
+        conv = (k,) + tuple(tspec.tnet_conv)
+        fc = (tspec.tnet_conv[-1],) + tuple(tspec.tnet_fc) + (k * k,)
+        for i in range(len(conv) - 1):
+            out += [(f"t{k}.conv{i}.w", (conv[i + 1], conv[i])), (f"t{k}.conv{i}.b", (conv[i + 1],)),
+                    (f"t{k}.conv{i}.bn.g", (conv[i + 1],)), (f"t{k}.conv{i}.bn.b", (conv[i + 1],))]
+        for i in range(len(fc) - 1):
+            out += [(f"t{k}.fc{i}.w", (fc[i], fc[i + 1])), (f"t{k}.fc{i}.b", (fc[i + 1],))]
+            if i < len(fc) - 2:
+                out += [(f"t{k}.fc{i}.bn.g", (fc[i + 1],)), (f"t{k}.fc{i}.bn.b", (fc[i + 1],))]
+    return out
+
+
+def pointnet_t_inputs(tspec: PointNetTSpec, seed: Optional[int] = None) -> Dict[str, object]:
+    """pointnet_cls_inputs plus the sub-networks' parameters (same initialisation rule; the last
+    Linear of a sub-network is scaled by 0.1 so that the matrices start near the identity)."""
+    spec = tspec.cls
+    inp = pointnet_cls_inputs(spec, seed)
+    seed = config_seed(spec.config_index) if seed is None else seed
+    rngs = model_streams(seed + 7919, spec.B)
+    shapes = pointnet_t_param_shapes(tspec)
+    sd = dict(shapes)
+    for b, rng in enumerate(rngs):
+        p = inp["params"][b]
+        for name, shape in shapes:
+            if name in p:
+                continue
+            conv = ".conv" in name
+            if name.endswith(".bn.g"):
+                p[name] = np.ones(shape, np.float32)
+            elif name.endswith(".bn.b"):
+                p[name] = np.zeros(shape, np.float32)
+            else:
+                wshape = shape if name.endswith(".w") else sd[name[:-2] + ".w"]
+                fan_in = wshape[1] if conv else wshape[0]
+                v = uniform_fan_in(rng, shape, fan_in, 6.0 if name.endswith(".w") else 1.0)
+                last = (not conv) and name.split(".")[1] == f"fc{len(tspec.tnet_fc)}"
+                p[name] = (v * (0.1 if last else 1.0)).astype(np.float32)
+    return inp
+
+
+# --------------------------------------------------------------------------
 # PointNet-segmentation-style fused array (BASELINE config 2)
 # --------------------------------------------------------------------------
 @dataclasses.dataclass(frozen=True)

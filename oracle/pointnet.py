@@ -44,130 +44,167 @@ def init_state(params: Dict[str, np.ndarray]) -> Dict[str, Dict[str, np.ndarray]
     return st
 
 
+def chain_cfg(spec, conv=None, fc="spec", conv_base=0, fused_tail=False, prefix="", dropout_p=None, fc_bn=None):
+    """Description of one chain: per-point layers conv[0] -> conv[-1] named
+    ``{prefix}conv{conv_base + i}``, then (unless fc is None) the max over points and the fully
+    connected layers ``{prefix}fc{i}``.  Defaults: the whole classification model of ``spec``."""
+    return dict(conv=tuple(spec.conv if conv is None else conv), fc=(tuple(spec.fc) if fc == "spec" else fc),
+                conv_base=conv_base, fused_tail=fused_tail, prefix=prefix, dtype=spec.dtype,
+                fc_bn=spec.fc_bn if fc_bn is None else fc_bn,
+                dropout_p=spec.dropout_p if dropout_p is None else dropout_p)
+
+
+def rounded_params(theta, dt):
+    """What the device multiplies with: weights and biases in the storage dtype, BatchNorm affine in fp32."""
+    return {k: (ops.store(v, dt) if k.endswith(".w") or (k.endswith(".b") and ".bn." not in k) else
+                np.asarray(v, np.float64)) for k, v in theta.items()}
+
+
+def chain_fwd(cfg, lp, a, drop_mask=None, running=None, new_running=None, bn_eps=1e-5, bn_momentum=0.1):
+    """Forward of one chain on a:[Nb,C,L].  Returns (out, ctx): out is the last activation
+    [Nb,C',L] (no head) or the last Linear's output [Nb,K]."""
+    dt, px, cb = cfg["dtype"], cfg["prefix"], cfg["conv_base"]
+    S = lambda v: ops.store(v, dt)
+    sdt = "f64" if dt == "f64" else "f32"       # saved statistics are float32 on the device
+    nconv = len(cfg["conv"]) - 1
+    head = cfg["fc"] is not None
+    nfc = len(cfg["fc"]) - 1 if head else 0
+    fused_tail = cfg["fused_tail"] and head
+    new_running = {} if new_running is None else new_running
+    saved = {}
+    a = np.asarray(a, np.float64)
+    pooled = idx = None
+    for i in range(nconv):
+        k = f"{px}conv{cb + i}"
+        rm = rv = None
+        if running is not None:
+            rm, rv = running[k + ".bn.rm"], running[k + ".bn.rv"]
+        if fused_tail and i == nconv - 1:
+            pooled, idx, mean, invstd, nrm, nrv, _ = ops.conv1x1_bn_maxpool_fwd(
+                a, lp[k + ".w"], lp[k + ".b"], lp[k + ".bn.g"], lp[k + ".bn.b"], bn_eps,
+                bn_momentum, rm, rv, ops.ACT_RELU)
+            mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
+            if running is not None:
+                new_running[k + ".bn.rm"], new_running[k + ".bn.rv"] = nrm, nrv
+            saved[k] = (a, None, None, mean, invstd)
+            pooled = S(pooled)
+            break
+        z = S(ops.conv1x1_fwd(a, lp[k + ".w"], lp[k + ".b"]))
+        y, mean, invstd, nrm, nrv = ops.bn_fwd(z, lp[k + ".bn.g"], lp[k + ".bn.b"], bn_eps, bn_momentum, rm, rv)
+        mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
+        if running is not None:
+            new_running[k + ".bn.rm"], new_running[k + ".bn.rv"] = nrm, nrv
+        saved[k] = (a, z, y, mean, invstd)
+        a = S(ops.act_fwd(y, ops.ACT_RELU))
+    ctx = dict(saved=saved, Lp=a.shape[2], idx=idx, pooled=None)
+    if not head:
+        return a, ctx
+    if not fused_tail:
+        pooled, idx = ops.maxpool_points_fwd(a)
+    ctx["idx"], ctx["pooled"] = idx, pooled
+
+    h = pooled
+    for i in range(nfc):
+        k = f"{px}fc{i}"
+        last = i == nfc - 1
+        zl = ops.linear_fwd(h, lp[k + ".w"], lp[k + ".b"])
+        if last:
+            z = S(zl)
+            saved[k] = (h,)
+            h = z
+            break
+        if cfg["fc_bn"]:
+            z = S(zl)
+            rm = rv = None
+            if running is not None:
+                rm, rv = running[k + ".bn.rm"], running[k + ".bn.rv"]
+            y, mean, invstd, nrm, nrv = ops.bn_fwd(z[:, :, None], lp[k + ".bn.g"], lp[k + ".bn.b"], bn_eps,
+                                                   bn_momentum, rm, rv)
+            mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
+            if running is not None:
+                new_running[k + ".bn.rm"], new_running[k + ".bn.rv"] = nrm, nrv
+            y = y[:, :, 0]
+            hn = S(ops.act_fwd(y, ops.ACT_RELU))
+            saved[k] = (h, z, y, mean, invstd)
+        else:
+            # Linear with the ReLU applied before the single store
+            hn = S(ops.act_fwd(zl, ops.ACT_RELU))
+            saved[k] = (h, hn)
+        if i == nfc - 2 and cfg["dropout_p"] > 0:
+            hn = S(ops.dropout_fwd(hn, drop_mask, cfg["dropout_p"]))
+        h = hn
+    return h, ctx
+
+
+def chain_bwd(cfg, lp, ctx, d, grads, drop_mask=None, want_dx=False):
+    """Backward of one chain from d = gradient of its output (stored).  Fills ``grads``;
+    returns the stored gradient of the chain's input if want_dx."""
+    dt, px, cb = cfg["dtype"], cfg["prefix"], cfg["conv_base"]
+    S = lambda v: ops.store(v, dt)
+    nconv = len(cfg["conv"]) - 1
+    head = cfg["fc"] is not None
+    nfc = len(cfg["fc"]) - 1 if head else 0
+    fused_tail = cfg["fused_tail"] and head
+    saved, idx = ctx["saved"], ctx["idx"]
+    for i in reversed(range(nfc)):
+        k = f"{px}fc{i}"
+        last = i == nfc - 1
+        if not last:
+            if i == nfc - 2 and cfg["dropout_p"] > 0:
+                d = S(ops.dropout_bwd(d, drop_mask, cfg["dropout_p"]))
+            if cfg["fc_bn"]:
+                hin, z, y, mean, invstd = saved[k]
+                dy = ops.act_bwd(y, d, ops.ACT_RELU)
+                dz, dg, dbt = ops.bn_bwd(z[:, :, None], dy[:, :, None], lp[k + ".bn.g"], mean, invstd)
+                grads[k + ".bn.g"], grads[k + ".bn.b"] = dg, dbt
+                d = S(dz[:, :, 0])
+            else:
+                hin, hout = saved[k]
+                d = S(ops.act_bwd(hout, d, ops.ACT_RELU))   # mask from the stored output
+        hin = saved[k][0]
+        dx, dw, db = ops.linear_bwd(hin, lp[k + ".w"], d)
+        grads[k + ".w"], grads[k + ".b"] = dw, db
+        d = S(dx)
+
+    if head and not fused_tail:
+        d = ops.maxpool_points_bwd(d, idx, ctx["Lp"])      # exact scatter of stored values
+    for i in reversed(range(nconv)):
+        k = f"{px}conv{cb + i}"
+        ain, z, y, mean, invstd = saved[k]
+        need_dx = i > 0 or want_dx
+        if fused_tail and i == nconv - 1:
+            dx, dw, db, dg, dbt = ops.conv1x1_bn_maxpool_bwd(ain, lp[k + ".w"], lp[k + ".b"], lp[k + ".bn.g"],
+                                                             lp[k + ".bn.b"], mean, invstd, d, idx, ops.ACT_RELU)
+            grads[k + ".bn.g"], grads[k + ".bn.b"], grads[k + ".w"], grads[k + ".b"] = dg, dbt, dw, db
+            if need_dx:
+                d = S(dx)
+            continue
+        dy = ops.act_bwd(y, d, ops.ACT_RELU)
+        dz, dg, dbt = ops.bn_bwd(z, dy, lp[k + ".bn.g"], mean, invstd)
+        grads[k + ".bn.g"], grads[k + ".bn.b"] = dg, dbt
+        dz = S(dz)
+        dx, dw, db = ops.conv1x1_bwd(ain, lp[k + ".w"], dz)
+        grads[k + ".w"], grads[k + ".b"] = dw, db
+        if need_dx:
+            d = S(dx)
+    return d if want_dx else None
+
+
 def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
                      bn_eps=1e-5, bn_momentum=0.1, fused_tail=False):
     """Forward + backward of one model.
 
     points:[Nb,3,L], labels:[Nb], drop_mask:[Nb,F] or None.
-    Returns dict(loss, logits, grads{name->float64}, pool_idx, acts{...}, running{...}).
+    Returns dict(loss, logits, grads{name->float64}, pool_idx, pooled, running{...}).
     """
-    dt = spec.dtype
-    S = lambda a: ops.store(a, dt)
-    sdt = "f64" if dt == "f64" else "f32"       # saved statistics are float32 on the device
-    lp = {k: (S(v) if k.endswith(".w") or (k.endswith(".b") and ".bn." not in k) else
-              np.asarray(v, np.float64)) for k, v in theta.items()}
-    nconv = len(spec.conv) - 1
-    nfc = len(spec.fc) - 1
+    cfg = chain_cfg(spec, fused_tail=fused_tail)
+    lp = rounded_params(theta, spec.dtype)
     new_running = {}
-    saved = {}
-
-    # ---------------- forward: per-point MLP
-    a = np.asarray(points, np.float64)
-    for i in range(nconv):
-        rm = rv = None
-        if running is not None:
-            rm, rv = running[f"conv{i}.bn.rm"], running[f"conv{i}.bn.rv"]
-        if fused_tail and i == nconv - 1:
-            pooled, idx, mean, invstd, nrm, nrv, _ = ops.conv1x1_bn_maxpool_fwd(
-                a, lp[f"conv{i}.w"], lp[f"conv{i}.b"], lp[f"conv{i}.bn.g"], lp[f"conv{i}.bn.b"], bn_eps,
-                bn_momentum, rm, rv, ops.ACT_RELU)
-            mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
-            if running is not None:
-                new_running[f"conv{i}.bn.rm"], new_running[f"conv{i}.bn.rv"] = nrm, nrv
-            saved[f"conv{i}"] = (a, None, None, mean, invstd)
-            pooled = S(pooled)
-            break
-        z = S(ops.conv1x1_fwd(a, lp[f"conv{i}.w"], lp[f"conv{i}.b"]))
-        y, mean, invstd, nrm, nrv = ops.bn_fwd(z, lp[f"conv{i}.bn.g"], lp[f"conv{i}.bn.b"],
-                                               bn_eps, bn_momentum, rm, rv)
-        mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
-        if running is not None:
-            new_running[f"conv{i}.bn.rm"], new_running[f"conv{i}.bn.rv"] = nrm, nrv
-        saved[f"conv{i}"] = (a, z, y, mean, invstd)
-        a = S(ops.act_fwd(y, ops.ACT_RELU))
-    if not fused_tail:
-        pooled, idx = ops.maxpool_points_fwd(a)
-    Lp = a.shape[2]
-
-    # ---------------- forward: head
-    h = pooled
-    for i in range(nfc):
-        last = i == nfc - 1
-        zl = ops.linear_fwd(h, lp[f"fc{i}.w"], lp[f"fc{i}.b"])
-        if last:
-            z = S(zl)
-            saved[f"fc{i}"] = (h,)
-            h = z
-            break
-        if spec.fc_bn:
-            z = S(zl)
-            rm = rv = None
-            if running is not None:
-                rm, rv = running[f"fc{i}.bn.rm"], running[f"fc{i}.bn.rv"]
-            y, mean, invstd, nrm, nrv = ops.bn_fwd(z[:, :, None], lp[f"fc{i}.bn.g"],
-                                                   lp[f"fc{i}.bn.b"], bn_eps, bn_momentum, rm, rv)
-            mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
-            if running is not None:
-                new_running[f"fc{i}.bn.rm"], new_running[f"fc{i}.bn.rv"] = nrm, nrv
-            y = y[:, :, 0]
-            hn = S(ops.act_fwd(y, ops.ACT_RELU))
-            saved[f"fc{i}"] = (h, z, y, mean, invstd)
-        else:
-            # Linear with the ReLU applied before the single store
-            hn = S(ops.act_fwd(zl, ops.ACT_RELU))
-            saved[f"fc{i}"] = (h, hn)
-        if i == nfc - 2 and spec.dropout_p > 0:
-            saved["drop_in"] = hn
-            hn = S(ops.dropout_fwd(hn, drop_mask, spec.dropout_p))
-        h = hn
-    logits = h
+    logits, ctx = chain_fwd(cfg, lp, points, drop_mask, running, new_running, bn_eps, bn_momentum)
     loss, dlogits = ops.softmax_xent(logits, labels)
-    d = S(dlogits)
-
-    # ---------------- backward: head
     grads = {}
-    for i in reversed(range(nfc)):
-        last = i == nfc - 1
-        if not last:
-            if i == nfc - 2 and spec.dropout_p > 0:
-                d = S(ops.dropout_bwd(d, drop_mask, spec.dropout_p))
-            if spec.fc_bn:
-                hin, z, y, mean, invstd = saved[f"fc{i}"]
-                dy = ops.act_bwd(y, d, ops.ACT_RELU)
-                dz, dg, dbt = ops.bn_bwd(z[:, :, None], dy[:, :, None], lp[f"fc{i}.bn.g"],
-                                         mean, invstd)
-                grads[f"fc{i}.bn.g"], grads[f"fc{i}.bn.b"] = dg, dbt
-                d = S(dz[:, :, 0])
-            else:
-                hin, hout = saved[f"fc{i}"]
-                d = S(ops.act_bwd(hout, d, ops.ACT_RELU))   # mask from the stored output
-        hin = saved[f"fc{i}"][0]
-        dx, dw, db = ops.linear_bwd(hin, lp[f"fc{i}.w"], d)
-        grads[f"fc{i}.w"], grads[f"fc{i}.b"] = dw, db
-        d = S(dx)
-
-    # ---------------- backward: pool and per-point MLP
-    if not fused_tail:
-        d = ops.maxpool_points_bwd(d, idx, Lp)      # exact scatter of stored values
-    for i in reversed(range(nconv)):
-        ain, z, y, mean, invstd = saved[f"conv{i}"]
-        if fused_tail and i == nconv - 1:
-            k = f"conv{i}"
-            dx, dw, db, dg, dbt = ops.conv1x1_bn_maxpool_bwd(ain, lp[k + ".w"], lp[k + ".b"], lp[k + ".bn.g"],
-                                                             lp[k + ".bn.b"], mean, invstd, d, idx, ops.ACT_RELU)
-            grads[k + ".bn.g"], grads[k + ".bn.b"], grads[k + ".w"], grads[k + ".b"] = dg, dbt, dw, db
-            if i > 0:
-                d = S(dx)
-            continue
-        dy = ops.act_bwd(y, d, ops.ACT_RELU)
-        dz, dg, dbt = ops.bn_bwd(z, dy, lp[f"conv{i}.bn.g"], mean, invstd)
-        grads[f"conv{i}.bn.g"], grads[f"conv{i}.bn.b"] = dg, dbt
-        dz = S(dz)
-        dx, dw, db = ops.conv1x1_bwd(ain, lp[f"conv{i}.w"], dz)
-        grads[f"conv{i}.w"], grads[f"conv{i}.b"] = dw, db
-        if i > 0:
-            d = S(dx)
-    return dict(loss=loss, logits=logits, grads=grads, pool_idx=idx, pooled=pooled,
+    chain_bwd(cfg, lp, ctx, ops.store(dlogits, spec.dtype), grads, drop_mask)
+    return dict(loss=loss, logits=logits, grads=grads, pool_idx=ctx["idx"], pooled=ctx["pooled"],
                 running=new_running)
 
 

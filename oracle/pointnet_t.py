@@ -1,0 +1,103 @@
+"""CPU oracle: one training step of ONE PointNet-cls-style model WITH the input / feature
+transform sub-networks, unfused.
+
+TEST INFRASTRUCTURE ONLY (see oracle/ops.py).
+
+Architecture (workload description of the point-cloud benchmark; appendix table of
+hyper-parameters lists the feature transform as a per-model switch): a transform sub-network is
+itself a small classification-style chain (per-point layers k -> 64 -> 128 -> 1024 with BatchNorm
+and ReLU, max over points, Linear 1024 -> 512 -> 256 with BatchNorm and ReLU, Linear 256 -> k*k);
+its output plus the identity is a k x k matrix per cloud that multiplies every point of the
+cloud.  The input transform (k = 3) acts on the coordinates, the feature transform (k = 64) on the
+output of the first per-point layer.  Reading: the k*k outputs are taken as T[o][c] (row = output
+channel), y[:, l] = T x[:, l]; the other orientation is the same model with the last Linear's
+output units relabelled.
+
+Storage rounding as in oracle/pointnet.py: every tensor kept between two operators is rounded once
+(T, the transformed points, their gradients).
+"""
+from __future__ import annotations
+
+from typing import Dict, List
+
+import numpy as np
+
+from . import ops
+from . import pointnet as pn
+
+
+def _tnet_cfg(tspec, k: int, fused_tail: bool):
+    s = tspec.cls
+    return pn.chain_cfg(s, conv=(k,) + tuple(tspec.tnet_conv), fc=(tspec.tnet_conv[-1],) + tuple(tspec.tnet_fc) + (k * k,),
+                        fused_tail=fused_tail, prefix=f"t{k}.", dropout_p=0.0, fc_bn=True)
+
+
+def _transform_fwd(tspec, k, lp, x, running, new_running, fused_tail, S):
+    cfg = _tnet_cfg(tspec, k, fused_tail)
+    o, ctx = pn.chain_fwd(cfg, lp, x, None, running, new_running)
+    T = S(o + np.eye(k).reshape(1, k * k)).reshape(-1, k, k)
+    return S(ops.point_transform_fwd(x, T)), (cfg, ctx, T, x)
+
+
+def _transform_bwd(lp, saved, dy, grads, S, want_dx):
+    """dy: stored gradient of the transformed tensor.  Returns the stored gradient of x if want_dx."""
+    cfg, ctx, T, x = saved
+    k = T.shape[1]
+    dx_direct, dT = ops.point_transform_bwd(x, T, dy)
+    dx_net = pn.chain_bwd(cfg, lp, ctx, S(dT).reshape(-1, k * k), grads, None, want_dx)
+    return S(S(dx_direct) + dx_net) if want_dx else None
+
+
+def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None, fused_tail=True):
+    """Forward + backward of one model.  Returns dict(loss, logits, grads, running, T3, T64)."""
+    s = tspec.cls
+    S = lambda v: ops.store(v, s.dtype)
+    lp = pn.rounded_params(theta, s.dtype)
+    new_running: Dict[str, np.ndarray] = {}
+    x = np.asarray(points, np.float64)
+    sv3 = sv64 = None
+    if tspec.input_transform:
+        x, sv3 = _transform_fwd(tspec, 3, lp, x, running, new_running, fused_tail, S)
+    cfg0 = pn.chain_cfg(s, conv=s.conv[:2], fc=None)
+    x1, ctx0 = pn.chain_fwd(cfg0, lp, x, None, running, new_running)
+    if tspec.feature_transform:
+        x1, sv64 = _transform_fwd(tspec, s.conv[1], lp, x1, running, new_running, fused_tail, S)
+    cfg1 = pn.chain_cfg(s, conv=s.conv[1:], conv_base=1, fused_tail=fused_tail)
+    logits, ctx1 = pn.chain_fwd(cfg1, lp, x1, drop_mask, running, new_running)
+    loss, dlogits = ops.softmax_xent(logits, labels)
+
+    grads: Dict[str, np.ndarray] = {}
+    d = pn.chain_bwd(cfg1, lp, ctx1, S(dlogits), grads, drop_mask, want_dx=True)
+    if tspec.feature_transform:
+        d = _transform_bwd(lp, sv64, d, grads, S, True)
+    d = pn.chain_bwd(cfg0, lp, ctx0, d, grads, None, want_dx=tspec.input_transform)
+    if tspec.input_transform:
+        _transform_bwd(lp, sv3, d, grads, S, False)
+    return dict(loss=loss, logits=logits, grads=grads, running=new_running,
+                T3=None if sv3 is None else sv3[2], T64=None if sv64 is None else sv64[2])
+
+
+def train_step(tspec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, fused_tail=True):
+    """One fwd + bwd + Adam step of one model; updates ``state`` (see oracle/pointnet.py) in place."""
+    out = forward_backward(tspec, state["theta"], points, labels, drop_mask, state["running"], fused_tail)
+    for k in state["theta"]:
+        g = ops.store(out["grads"][k], "f32")
+        th, m, v = ops.adam_step(state["theta"][k], g, state["m"][k], state["v"][k],
+                                 hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["wd"], t)
+        state["theta"][k] = th.astype(np.float32)
+        state["m"][k] = m.astype(np.float32)
+        state["v"][k] = v.astype(np.float32)
+    for k, val in out["running"].items():
+        state["running"][k] = np.asarray(val, np.float32)
+    return out
+
+
+def array_train_step(tspec, states: List[dict], inp: dict, t: int, fused_tail=True):
+    """The array's reference: B separate unfused runs, one after another."""
+    outs = []
+    for b in range(tspec.cls.B):
+        hp = {k: float(inp[k][b]) for k in ("lr", "beta1", "beta2", "eps", "wd")}
+        mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
+        outs.append(train_step(tspec, states[b], inp["points"][:, 3 * b:3 * b + 3, :], inp["labels"][b], hp, t,
+                               mask, fused_tail))
+    return outs
