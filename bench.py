@@ -39,6 +39,7 @@ class Tracer:
                      "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_fwd",
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
                      "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
+                     "point_transform_fwd", "point_transform_bwd",
                      "conv1x1_bn_maxpool_bwd")
 
     def __init__(self, hb, torch):
@@ -117,6 +118,8 @@ def kernel_label(name, a):
         return name + "_kernel"
     if name == "softmax_xent_rows":
         return "xent_rows_kernel"
+    if name in ("point_transform_fwd", "point_transform_bwd"):
+        return name + ": batched GEMM per (model, cloud)"
     if name in ("add_sample_bias", "add_strided"):
         return "row_add_kernel"
     if name == "sum_points":
@@ -254,6 +257,12 @@ def algorithmic_bytes(name, a):
         return 3 * a[0] * a[1] * a[2] * a[3] * _es(a[4])
     if name == "sum_points":
         return a[0] * a[1] * a[2] * a[3] * _es(a[4])
+    if name == "point_transform_fwd":         # x in, y out, one small matrix per cloud
+        B, Nb, Ci, Co, L, dt = a[:6]
+        return B * Nb * ((Ci + Co) * L + Ci * Co) * _es(dt)
+    if name == "point_transform_bwd":         # x, dy in; dx (if asked for) and the matrix gradient out
+        B, Nb, Ci, Co, L, dt = a[:6]
+        return B * Nb * ((Ci + Co + (Ci if a[11] is not None else 0)) * L + 2 * Ci * Co) * _es(dt)
     if name == "act_fwd":
         return 2 * a[0] * _es(a[1])
     if name in ("act_bwd", "add"):
@@ -371,6 +380,17 @@ class Workload:
             self.config = {"workload": self.spec.name, "B": self.spec.B, "batch_per_model": self.spec.Nb,
                            "points": self.spec.L, "conv": list(self.spec.conv), "fc": list(self.spec.fc),
                            "step": "fwd+bwd+Adam"}
+        elif name == "c1t":
+            from oracle import pointnet_t as oracle_model
+            self.spec = hi.PointNetTSpec(cls=hi.spec_c1())
+            self.inp = hi.pointnet_t_inputs(self.spec)
+            self.cls = arrays.FusedPointNetClsT
+            self.per_model_keys = ("labels",)
+            c = self.spec.cls
+            self.config = {"workload": self.spec.name, "B": c.B, "batch_per_model": c.Nb, "points": c.L,
+                           "conv": list(c.conv), "fc": list(c.fc),
+                           "transform_subnetworks": {"sizes": hi.tnet_sizes(self.spec), "conv": list(self.spec.tnet_conv),
+                                                     "fc": list(self.spec.tnet_fc)}, "step": "fwd+bwd+Adam"}
         elif name == "c2":
             from oracle import pointnet_seg as oracle_model
             self.spec = hi.spec_c2()
@@ -413,11 +433,11 @@ class Workload:
 
     def one_model(self, b):
         """(spec, inputs) of model b alone: the serial scheme's unit."""
-        s1 = dataclasses.replace(self.spec, B=1)
+        s1 = self.spec.with_cls(B=1) if self.name == "c1t" else dataclasses.replace(self.spec, B=1)
         i1 = dict(self.inp)
-        if self.name in ("c0", "c1", "c2"):
+        if self.name in ("c0", "c1", "c1t", "c2"):
             i1["points"] = np.ascontiguousarray(self.inp["points"][:, 3 * b:3 * b + 3])
-        if self.name in ("c0", "c1"):
+        if self.name in ("c0", "c1", "c1t"):
             i1["drop_mask"] = None if self.inp["drop_mask"] is None else self.inp["drop_mask"][b:b + 1]
         for k in self.per_model_keys + ("lr", "beta1", "beta2", "eps", "wd"):
             i1[k] = self.inp[k][b:b + 1]
@@ -438,6 +458,11 @@ class Workload:
             inp = hi.pointnet_cls_inputs(small)
             nsamp = small.Nb
             what = f"1 model x {small.Nb} clouds x {small.L} points"
+        elif self.name == "c1t":
+            small = self.spec.with_cls(B=1, Nb=8)
+            inp = hi.pointnet_t_inputs(small)
+            nsamp = small.Nb
+            what = f"1 model x {small.Nb} clouds x {small.L} points, with transform sub-networks"
         elif self.name == "c2":
             small = dataclasses.replace(self.spec, B=1, Nb=2)
             inp = hi.pointnet_seg_inputs(small)
@@ -483,7 +508,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4", "t0"])
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c1t", "c2", "c3", "c4", "t0"])
     ap.add_argument("--unfused", type=int, default=0,
                     help="config 1 only: run the first K per-point layers (and their share of Adam) model by model "
                          "(partial fusion); the headline line is K = 0")

@@ -184,9 +184,22 @@ class PointNetTSpec:
     input_transform: bool = True
     feature_transform: bool = True
 
+    # what generic drivers ask of a spec
+    B = property(lambda self: self.cls.B)
+    Nb = property(lambda self: self.cls.Nb)
+    L = property(lambda self: self.cls.L)
+    dtype = property(lambda self: self.cls.dtype)
+    name = property(lambda self: self.cls.name + "_transforms")
+
+    def with_cls(self, **kw) -> "PointNetTSpec":
+        return dataclasses.replace(self, cls=dataclasses.replace(self.cls, **kw))
+
 
 def tnet_sizes(tspec: PointNetTSpec) -> List[int]:
-    return ([3] if tspec.input_transform else []) + ([tspec.cls.conv[1]] if tspec.feature_transform else [])
+    """Matrix sizes of the sub-networks, largest first: in arena order the only parameter whose
+    size is not a multiple of 8 (the 9 biases of the 3x3 matrix) then comes last, so every weight
+    matrix of every model starts on a 16-byte boundary."""
+    return ([tspec.cls.conv[1]] if tspec.feature_transform else []) + ([3] if tspec.input_transform else [])
 
 
 def pointnet_t_param_shapes(tspec: PointNetTSpec) -> List[Tuple[str, Tuple[int, ...]]]:

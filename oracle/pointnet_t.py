@@ -25,6 +25,8 @@ import numpy as np
 from . import ops
 from . import pointnet as pn
 
+init_state = pn.init_state
+
 
 def _tnet_cfg(tspec, k: int, fused_tail: bool):
     s = tspec.cls
@@ -32,24 +34,31 @@ def _tnet_cfg(tspec, k: int, fused_tail: bool):
                         fused_tail=fused_tail, prefix=f"t{k}.", dropout_p=0.0, fc_bn=True)
 
 
-def _transform_fwd(tspec, k, lp, x, running, new_running, fused_tail, S):
+def _transform_fwd(tspec, k, lp, x, running, new_running, fused_tail, S, T_given=None):
     cfg = _tnet_cfg(tspec, k, fused_tail)
     o, ctx = pn.chain_fwd(cfg, lp, x, None, running, new_running)
-    T = S(o + np.eye(k).reshape(1, k * k)).reshape(-1, k, k)
-    return S(ops.point_transform_fwd(x, T)), (cfg, ctx, T, x)
+    T_own = S(o + np.eye(k).reshape(1, k * k)).reshape(-1, k, k)
+    T = T_own if T_given is None else np.asarray(T_given, np.float64).reshape(-1, k, k)
+    return S(ops.point_transform_fwd(x, T)), (cfg, ctx, T, x, T_own)
 
 
 def _transform_bwd(lp, saved, dy, grads, S, want_dx):
     """dy: stored gradient of the transformed tensor.  Returns the stored gradient of x if want_dx."""
-    cfg, ctx, T, x = saved
+    cfg, ctx, T, x, _ = saved
     k = T.shape[1]
     dx_direct, dT = ops.point_transform_bwd(x, T, dy)
     dx_net = pn.chain_bwd(cfg, lp, ctx, S(dT).reshape(-1, k * k), grads, None, want_dx)
     return S(S(dx_direct) + dx_net) if want_dx else None
 
 
-def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None, fused_tail=True):
-    """Forward + backward of one model.  Returns dict(loss, logits, grads, running, T3, T64)."""
+def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None, fused_tail=True, T_given=None):
+    """Forward + backward of one model.  Returns dict(loss, logits, grads, running, T3, T64).
+
+    T_given: {k: [Nb,k,k]} replaces the stored matrix of a sub-network by a given one (the value a
+    device run stored) from there on: a matrix entry near 1 has a storage ulp of 2^-8 in bf16, and
+    one such last-bit difference moves every point of the cloud, after which the two runs take
+    different argmax / ReLU decisions.  T3 / T64 in the result are the oracle's own matrices."""
+    T_given = T_given or {}
     s = tspec.cls
     S = lambda v: ops.store(v, s.dtype)
     lp = pn.rounded_params(theta, s.dtype)
@@ -57,11 +66,11 @@ def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None,
     x = np.asarray(points, np.float64)
     sv3 = sv64 = None
     if tspec.input_transform:
-        x, sv3 = _transform_fwd(tspec, 3, lp, x, running, new_running, fused_tail, S)
+        x, sv3 = _transform_fwd(tspec, 3, lp, x, running, new_running, fused_tail, S, T_given.get(3))
     cfg0 = pn.chain_cfg(s, conv=s.conv[:2], fc=None)
     x1, ctx0 = pn.chain_fwd(cfg0, lp, x, None, running, new_running)
     if tspec.feature_transform:
-        x1, sv64 = _transform_fwd(tspec, s.conv[1], lp, x1, running, new_running, fused_tail, S)
+        x1, sv64 = _transform_fwd(tspec, s.conv[1], lp, x1, running, new_running, fused_tail, S, T_given.get(s.conv[1]))
     cfg1 = pn.chain_cfg(s, conv=s.conv[1:], conv_base=1, fused_tail=fused_tail)
     logits, ctx1 = pn.chain_fwd(cfg1, lp, x1, drop_mask, running, new_running)
     loss, dlogits = ops.softmax_xent(logits, labels)
@@ -74,12 +83,12 @@ def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None,
     if tspec.input_transform:
         _transform_bwd(lp, sv3, d, grads, S, False)
     return dict(loss=loss, logits=logits, grads=grads, running=new_running,
-                T3=None if sv3 is None else sv3[2], T64=None if sv64 is None else sv64[2])
+                T3=None if sv3 is None else sv3[4], T64=None if sv64 is None else sv64[4])
 
 
-def train_step(tspec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, fused_tail=True):
+def train_step(tspec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, fused_tail=True, T_given=None):
     """One fwd + bwd + Adam step of one model; updates ``state`` (see oracle/pointnet.py) in place."""
-    out = forward_backward(tspec, state["theta"], points, labels, drop_mask, state["running"], fused_tail)
+    out = forward_backward(tspec, state["theta"], points, labels, drop_mask, state["running"], fused_tail, T_given)
     for k in state["theta"]:
         g = ops.store(out["grads"][k], "f32")
         th, m, v = ops.adam_step(state["theta"][k], g, state["m"][k], state["v"][k],
@@ -92,12 +101,12 @@ def train_step(tspec, state, points, labels, hp: Dict[str, float], t: int, drop_
     return out
 
 
-def array_train_step(tspec, states: List[dict], inp: dict, t: int, fused_tail=True):
-    """The array's reference: B separate unfused runs, one after another."""
+def array_train_step(tspec, states: List[dict], inp: dict, t: int, fused_tail=True, T_given=None):
+    """The array's reference: B separate unfused runs, one after another.  T_given: per model, see forward_backward."""
     outs = []
     for b in range(tspec.cls.B):
         hp = {k: float(inp[k][b]) for k in ("lr", "beta1", "beta2", "eps", "wd")}
         mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
         outs.append(train_step(tspec, states[b], inp["points"][:, 3 * b:3 * b + 3, :], inp["labels"][b], hp, t,
-                               mask, fused_tail))
+                               mask, fused_tail, None if T_given is None else T_given[b]))
     return outs

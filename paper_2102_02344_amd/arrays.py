@@ -1086,3 +1086,258 @@ class FusedTransformerLM(ParamArena):
         hb.embedding_bwd(B, R, V, E, dt, d, self.tokens, self.scale, self.g("emb"))
         P("embedding_bwd", dy=d, idx=self.tokens, dtable=self.g("emb"))
         return self.loss
+
+
+class _PointChain:
+    """One chain of a point-cloud model inside a ParamArena: per-point layers (k=1 convolution,
+    BatchNorm, ReLU) named ``{prefix}conv{conv_base+i}``, then, if ``fc`` is given, the max over
+    points and the fully connected layers ``{prefix}fc{i}`` (hidden ones with BatchNorm and ReLU,
+    dropout after the last hidden one).  The last per-point layer, its BatchNorm, ReLU and the max
+    run as one operator where the library has it.  ``fwd`` returns the chain's output tensor,
+    ``bwd`` takes the gradient of that tensor."""
+
+    def __init__(self, arena, prefix, conv, fc, conv_base, fc_bn=True, dropout_p=0.0, drop_mask=None):
+        A = self.A = arena
+        self.px, self.conv, self.fc, self.cb = prefix, tuple(conv), None if fc is None else tuple(fc), conv_base
+        self.fc_bn, self.dropout_p, self.drop_mask = fc_bn, dropout_p, drop_mask
+        B, Nb, L, dt = A.B, A.Nb, A.L, A.dt
+        act = dict(dtype=A.tdt, device=A.dev)
+        f32 = dict(dtype=torch.float32, device=A.dev)
+        self.nconv = len(self.conv) - 1
+        self.head = self.fc is not None
+        self.nfc = len(self.fc) - 1 if self.head else 0
+        self.fused_tail = False
+        ws = 4
+        if self.head and self.nconv >= 2:
+            geo = (B, Nb, self.conv[-2], self.conv[-1], L, dt)
+            wt = A.w(f"{prefix}conv{conv_base + self.nconv - 1}.w")     # the one-operator tail wants 16-byte aligned weights
+            self.fused_tail = hb.conv1x1_bn_maxpool_fwd_workspace_bytes(*geo) > 0 and wt.data_ptr() % 16 == 0
+            if self.fused_tail:
+                ws = max(ws, hb.conv1x1_bn_maxpool_fwd_workspace_bytes(*geo), hb.conv1x1_bn_maxpool_bwd_workspace_bytes(*geo))
+        nz = self.nconv - 1 if self.fused_tail else self.nconv
+        self.z = [torch.empty(Nb, B * c, L, **act) for c in self.conv[1:1 + nz]]
+        na = self.nconv if not self.head else self.nconv - 1            # a chain without a head keeps its last activation
+        self.a = [torch.empty(Nb, B * c, L, **act) for c in self.conv[1:1 + na]]
+        cmax = max(self.conv)
+        self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
+        for i in range(self.nconv):
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt))
+        if self.head:
+            Cp = self.conv[-1]
+            self.pooled = torch.empty(B, Nb, Cp, **act)
+            self.pool_idx = torch.empty(B, Nb, Cp, dtype=torch.int32, device=A.dev)
+            if self.fused_tail:
+                self.zhit = torch.empty(B, Nb, Cp, **f32)
+                self.moments = torch.empty(hb.conv1x1_bn_maxpool_saved_floats(B, self.conv[-2], Cp), **f32)
+            self.fz = [torch.empty(B, Nb, f, **act) for f in self.fc[1:]]
+            self.fh = [torch.empty(B, Nb, f, **act) for f in self.fc[1:-1]]
+            self.fdrop = torch.empty(B, Nb, self.fc[-2], **act) if dropout_p > 0 else None
+            self.fd = [torch.empty(B * Nb * max(self.fc), **act) for _ in range(2)]
+            for i in range(self.nfc):
+                ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, self.fc[i], self.fc[i + 1], dt),
+                         hb.linear_fwd_workspace_bytes(B, Nb, self.fc[i], self.fc[i + 1], dt))
+        self.ws_bytes = ws
+
+    def _bn(self, k):
+        A = self.A
+        return (A.master(k + ".bn.g"), A.master(k + ".bn.b"), A.BN_EPS, A.BN_MOMENTUM, A.running[k + ".bn.rm"],
+                A.running[k + ".bn.rv"], A.saved[k + ".bn.mean"], A.saved[k + ".bn.invstd"])
+
+    def fwd(self, x):
+        """x: [Nb, B*conv[0], L] contiguous.  Returns the last activation (no head) or the last Linear's output."""
+        A = self.A
+        B, Nb, L, dt, ws = A.B, A.Nb, A.L, A.dt, A.ws
+        self.x_in = x
+        ci = self.conv[0]
+        for i in range(self.nconv):
+            co, k = self.conv[i + 1], f"{self.px}conv{self.cb + i}"
+            tail = self.head and i == self.nconv - 1
+            if tail and self.fused_tail:
+                hb.conv1x1_bn_maxpool_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), A.w(k + ".w"), A.w(k + ".b"), *self._bn(k),
+                                          self.pooled, self.pool_idx, (Nb * co, co, 1), self.zhit, self.moments,
+                                          hb.ACT_RELU, 0.0, ws)
+                break
+            hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), A.w(k + ".w"), A.w(k + ".b"), self.z[i], _cs(B, co, L))
+            if tail:
+                hb.bn_fwd_maxpool(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *self._bn(k), self.pooled, self.pool_idx,
+                                  (Nb * co, co, 1), hb.ACT_RELU)
+                break
+            hb.bn_fwd(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *self._bn(k), self.a[i], _cs(B, co, L), hb.ACT_RELU)
+            x, ci = self.a[i], co
+        if not self.head:
+            return x
+        h = self.pooled
+        for i in range(self.nfc):
+            fx, fy, k = self.fc[i], self.fc[i + 1], f"{self.px}fc{i}"
+            last = i == self.nfc - 1
+            if last or self.fc_bn:
+                hb.linear_fwd_ws(B, Nb, fx, fy, dt, h, A.w(k + ".w"), A.w(k + ".b"), self.fz[i], workspace=ws)
+                if last:
+                    return self.fz[i]
+                ls = (Nb * fy, fy, 1, 1)
+                hb.bn_fwd(B, Nb, fy, 1, dt, self.fz[i], ls, *self._bn(k), self.fh[i], ls, hb.ACT_RELU)
+            else:
+                hb.linear_fwd_ws(B, Nb, fx, fy, dt, h, A.w(k + ".w"), A.w(k + ".b"), self.fh[i], hb.ACT_RELU, workspace=ws)
+            h = self.fh[i]
+            if i == self.nfc - 2 and self.dropout_p > 0:
+                hb.dropout(B * Nb * fy, dt, h, self.drop_mask, self.dropout_p, self.fdrop)
+                h = self.fdrop
+
+    def bwd(self, d, want_dx):
+        """d: gradient of the chain's output (flat, storage dtype).  Parameter gradients go to the
+        arena; returns the gradient of the chain's input (flat view of an own buffer) if want_dx."""
+        A = self.A
+        B, Nb, L, dt, ws = A.B, A.Nb, A.L, A.dt, A.ws
+        cur = 0
+        for i in reversed(range(self.nfc)):
+            fx, fy, k = self.fc[i], self.fc[i + 1], f"{self.px}fc{i}"
+            last = i == self.nfc - 1
+            if not last:
+                n = B * Nb * fy
+                if i == self.nfc - 2 and self.dropout_p > 0:
+                    nd = self.fd[cur ^ 1][:n]
+                    hb.dropout(n, dt, d, self.drop_mask, self.dropout_p, nd)
+                    d, cur = nd, cur ^ 1
+                nd = self.fd[cur ^ 1][:n]
+                if self.fc_bn:
+                    ls = (Nb * fy, fy, 1, 1)
+                    hb.bn_bwd(B, Nb, fy, 1, dt, self.fz[i], ls, d, ls, A.master(k + ".bn.g"), A.master(k + ".bn.b"),
+                              A.saved[k + ".bn.mean"], A.saved[k + ".bn.invstd"], nd, ls, A.g(k + ".bn.g"),
+                              A.g(k + ".bn.b"), hb.ACT_RELU, 0.0, A.g(k + ".b"))
+                else:
+                    hb.act_bwd(n, dt, self.fh[i], d, nd, hb.ACT_RELU, 0.0, 1)
+                d, cur = nd, cur ^ 1
+            if i == 0:
+                hin = self.pooled
+            elif i == self.nfc - 1 and self.dropout_p > 0:
+                hin = self.fdrop
+            else:
+                hin = self.fh[i - 1]
+            nd = self.fd[cur ^ 1][:B * Nb * fx]
+            own_db = A.g(k + ".b") if (last or not self.fc_bn) else None
+            hb.linear_bwd(B, Nb, fx, fy, dt, hin, A.w(k + ".w"), d, nd, A.g(k + ".w"), own_db, ws)
+            d, cur = nd, cur ^ 1
+
+        da, cur = d, 0
+        for i in reversed(range(self.nconv)):
+            ci, co, k = self.conv[i], self.conv[i + 1], f"{self.px}conv{self.cb + i}"
+            cs, xs = _cs(B, co, L), _cs(B, ci, L)
+            xin = self.x_in if i == 0 else self.a[i - 1]
+            need_dx = i > 0 or want_dx
+            dxin = self.dbuf[cur][:Nb * B * ci * L] if need_dx else None
+            tail = self.head and i == self.nconv - 1
+            bn = (A.master(k + ".bn.g"), A.master(k + ".bn.b"), A.saved[k + ".bn.mean"], A.saved[k + ".bn.invstd"])
+            if tail and self.fused_tail:
+                # the operator always writes dX: give it a buffer even when nobody reads it
+                dxo = dxin if need_dx else self.dbuf[cur][:Nb * B * ci * L]
+                hb.conv1x1_bn_maxpool_bwd(B, Nb, ci, co, L, dt, xin, xs, A.w(k + ".w"), A.w(k + ".b"), None, None, self.zhit,
+                                          self.moments, da, self.pool_idx, (Nb * co, co, 1), *bn, dxo, xs, A.g(k + ".w"),
+                                          A.g(k + ".b"), A.g(k + ".bn.g"), A.g(k + ".bn.b"), hb.ACT_RELU, 0.0, ws)
+                da = dxin
+                continue
+            dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
+            if tail:
+                hb.bn_bwd_maxpool(B, Nb, co, L, dt, self.z[i], cs, da, self.pool_idx, (Nb * co, co, 1), *bn, dz, cs,
+                                  A.g(k + ".bn.g"), A.g(k + ".bn.b"), hb.ACT_RELU, 0.0, A.g(k + ".b"))
+            else:
+                hb.bn_bwd(B, Nb, co, L, dt, self.z[i], cs, da, cs, *bn, dz, cs, A.g(k + ".bn.g"), A.g(k + ".bn.b"),
+                          hb.ACT_RELU, 0.0, A.g(k + ".b"))
+            if need_dx:
+                hb.conv1x1_bwd(B, Nb, ci, co, L, dt, None, None, A.w(k + ".w"), dz, cs, dxin, xs, None, None, ws)
+            hb.conv1x1_bwd(B, Nb, ci, co, L, dt, xin, xs, None, dz, cs, None, None, A.g(k + ".w"), None, ws)
+            da = dxin
+        return da if want_dx else None
+
+
+class FusedPointNetClsT(ParamArena):
+    """PointNet-classification-style array whose models carry the input (3x3) and / or feature
+    (64x64) transform sub-networks: each is a small chain of the same fused operators whose output
+    plus the identity is a matrix per (model, cloud), applied to all points of the cloud by
+    ``point_transform_fwd``; its gradient comes back through ``point_transform_bwd``."""
+
+    BN_EPS = 1e-5
+    BN_MOMENTUM = 0.1
+
+    def __init__(self, tspec, inp: dict, device: str = "cuda"):
+        import hfta_inputs as hi
+        spec = tspec.cls
+        self.tspec, self.spec = tspec, spec
+        self.B, self.Nb, self.L = spec.B, spec.Nb, spec.L
+        self.dtype, self.dt, self.tdt = spec.dtype, _DT[spec.dtype], _TDT[spec.dtype]
+        self.dev = torch.device(device)
+        B, Nb, L = self.B, self.Nb, self.L
+        self._init_arena(hi.pointnet_t_param_shapes(tspec), B, inp, spec.dtype, self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        act = dict(dtype=self.tdt, device=self.dev)
+        self.running: Dict[str, torch.Tensor] = {}
+        self.saved: Dict[str, torch.Tensor] = {}
+        for name, shp in self.shapes:
+            if name.endswith(".bn.g"):
+                k = name[:-2]
+                self.running[k + ".rm"] = torch.zeros(B * shp[0], **f32)
+                self.running[k + ".rv"] = torch.ones(B * shp[0], **f32)
+                self.saved[k + ".mean"] = torch.empty(B * shp[0], **f32)
+                self.saved[k + ".invstd"] = torch.empty(B * shp[0], **f32)
+        self.points = torch.from_numpy(np.ascontiguousarray(inp["points"])).to(self.dev).to(self.tdt)
+        self.labels = torch.from_numpy(np.ascontiguousarray(inp["labels"])).to(self.dev)
+        self.drop_mask = None
+        if spec.dropout_p > 0:
+            self.drop_mask = torch.from_numpy(np.ascontiguousarray(inp["drop_mask"])).to(self.dev)
+        self.loss = torch.empty(B, **f32)
+
+        def tnet(k):
+            ch = _PointChain(self, f"t{k}.", (k,) + tuple(tspec.tnet_conv),
+                             (tspec.tnet_conv[-1],) + tuple(tspec.tnet_fc) + (k * k,), 0)
+            eye = torch.eye(k, **act).reshape(1, 1, k * k).expand(B, Nb, k * k).contiguous()
+            return dict(k=k, chain=ch, eye=eye, T=torch.empty(B, Nb, k, k, **act), dT=torch.empty(B, Nb, k, k, **act),
+                        y=torch.empty(Nb, B * k, L, **act), dx=torch.empty(Nb * B * k * L, **act))
+
+        self.t_in = tnet(3) if tspec.input_transform else None
+        self.block0 = _PointChain(self, "", spec.conv[:2], None, 0)
+        self.t_feat = tnet(spec.conv[1]) if tspec.feature_transform else None
+        self.rest = _PointChain(self, "", spec.conv[1:], spec.fc, 1, spec.fc_bn, spec.dropout_p, self.drop_mask)
+        self.dlogits = torch.empty(B * Nb * spec.fc[-1], **act)
+        chains = [self.block0, self.rest] + [t["chain"] for t in (self.t_in, self.t_feat) if t is not None]
+        self.ws = torch.empty(max(c.ws_bytes for c in chains), dtype=torch.uint8, device=self.dev)
+
+    def _transform_fwd(self, t, x):
+        B, Nb, L, dt, k = self.B, self.Nb, self.L, self.dt, t["k"]
+        o = t["chain"].fwd(x)
+        hb.add(B * Nb * k * k, dt, o, t["eye"], t["T"])
+        t["x"] = x
+        hb.point_transform_fwd(B, Nb, k, k, L, dt, x, _cs(B, k, L), t["T"], t["y"], _cs(B, k, L))
+        return t["y"]
+
+    def _transform_bwd(self, t, dy, want_dx):
+        B, Nb, L, dt, k = self.B, self.Nb, self.L, self.dt, t["k"]
+        cs = _cs(B, k, L)
+        hb.point_transform_bwd(B, Nb, k, k, L, dt, t["x"], cs, t["T"], dy, cs, t["dx"] if want_dx else None,
+                               cs if want_dx else None, t["dT"])
+        dnet = t["chain"].bwd(t["dT"].view(-1), want_dx)
+        if not want_dx:
+            return None
+        hb.add(Nb * B * k * L, dt, t["dx"], dnet, t["dx"])
+        return t["dx"]
+
+    def forward_backward(self):
+        s, B, Nb, dt = self.spec, self.B, self.Nb, self.dt
+        x = self.points
+        if self.t_in is not None:
+            x = self._transform_fwd(self.t_in, x)
+        x = self.block0.fwd(x)
+        if self.t_feat is not None:
+            x = self._transform_fwd(self.t_feat, x)
+        logits = self.rest.fwd(x)
+        hb.softmax_xent(B, Nb, s.fc[-1], dt, logits, self.labels, self.loss, self.dlogits)
+        d = self.rest.bwd(self.dlogits, True)
+        if self.t_feat is not None:
+            d = self._transform_bwd(self.t_feat, d, True)
+        d = self.block0.bwd(d, self.t_in is not None)
+        if self.t_in is not None:
+            self._transform_bwd(self.t_in, d, False)
+        return self.loss
+
+    def train_step(self):
+        loss = self.forward_backward()
+        self.adam()
+        return loss

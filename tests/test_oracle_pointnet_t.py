@@ -121,3 +121,28 @@ def test_storage_rounding_and_train_step():
         assert len(moved) >= len(before[b]) - 8, sorted(set(before[b]) - set(moved))   # biases in front of a BatchNorm stay
         assert any(k.startswith("t3.") for k in moved) and any(k.startswith("t5.") for k in moved)
         assert set(o["running"]) == {k[:-2] + s for k in before[b] if k.endswith(".bn.g") for s in (".rm", ".rv")}
+
+
+def test_given_matrices():
+    """Handing the oracle its own stored matrices changes nothing; handing it other matrices gives
+    the model whose transform output is that matrix (here: the identity = no transform): same loss,
+    same gradients downstream of the feature transform (the first layer still receives the gradient
+    that flows back through the sub-network)."""
+    ts = tiny()
+    inp = hi.pointnet_t_inputs(ts, seed=14)
+    theta = {k: v.astype(np.float64) for k, v in inp["params"][0].items()}
+    pts, lab, mask = inp["points"][:, 0:3, :], inp["labels"][0], inp["drop_mask"][0]
+    own = opt.forward_backward(ts, theta, pts, lab, mask)
+    same = opt.forward_backward(ts, theta, pts, lab, mask, T_given={3: own["T3"], ts.cls.conv[1]: own["T64"]})
+    assert same["loss"] == own["loss"] and all(np.array_equal(same["grads"][k], own["grads"][k]) for k in theta)
+    Nb, k2 = ts.cls.Nb, ts.cls.conv[1]
+    eye = {3: np.broadcast_to(np.eye(3), (Nb, 3, 3)), k2: np.broadcast_to(np.eye(k2), (Nb, k2, k2))}
+    ident = opt.forward_backward(ts, theta, pts, lab, mask, T_given=eye)
+    plain = opn.forward_backward(ts.cls, {k: v for k, v in theta.items() if not k.startswith("t")}, pts, lab, mask,
+                                 fused_tail=True)
+    assert abs(ident["loss"] - plain["loss"]) < 1e-13
+    for k, g in plain["grads"].items():
+        if not k.startswith("conv0."):
+            assert np.abs(ident["grads"][k] - g).max() <= 1e-11 * max(np.abs(g).max(), 1e-3), k
+    assert np.abs(ident["grads"]["conv0.w"] - plain["grads"]["conv0.w"]).max() > 1e-6
+    assert np.array_equal(ident["T3"], own["T3"])          # the oracle's own matrices are still reported
