@@ -246,6 +246,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv_gemm_kernel(ConvArgs p) {
 // (4x fewer MFMAs and gathers for 4x4 / stride 2).
 struct ConvDxArgs {
   const void* Wt; const void* dY; void* dX;
+  const void* Wp;    // weights regrouped per parity class, [b][class][Ci][K] (k-contiguous), or nullptr
   int B, Nb, Ci, Co, H, W, Ho, Wo, kh, kw, stride, pad;
   int KJ;            // taps per class and axis: ceil(k / stride)
   int Hqm, Wqm;      // class pixel grid (maximum over classes)
@@ -254,7 +255,29 @@ struct ConvDxArgs {
   FastDiv d_kj, d_kjkj, d_wqm, d_s;
 };
 
+// Regroups the weights for conv_dx_kernel: Wp[b][class][m][k = (o, jy, jx)] = W[b][o][m][ry + s jy][rx + s jx]
+// (zero where the tap falls outside the kernel), so that the data-gradient kernel reads its A operand
+// in 16-byte pieces instead of gathering single taps.
 template <typename T>
+__global__ __launch_bounds__(256) void conv_dx_pack_w_kernel(ConvDxArgs p, T* __restrict__ Wp, int64_t count) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const int kk = (int)(i % p.K);
+  int64_t r = i / p.K;
+  const int m = (int)(r % p.Ci); r /= p.Ci;
+  const int ncls = p.stride * p.stride;
+  const int cls = (int)(r % ncls), b = (int)(r / ncls);
+  int py, px, o, rr, jy, jx;
+  p.d_s.divmod(cls, py, px);
+  const int ry = (py + p.pad) % p.stride, rx = (px + p.pad) % p.stride;
+  p.d_kjkj.divmod(kk, o, rr);
+  p.d_kj.divmod(rr, jy, jx);
+  const int ky = ry + p.stride * jy, kx = rx + p.stride * jx;
+  const T* Wt = reinterpret_cast<const T*>(p.Wt);
+  Wp[i] = (ky < p.kh && kx < p.kw) ? Wt[(((int64_t)b * p.Co + o) * p.Ci + m) * (p.kh * p.kw) + ky * p.kw + kx] : T(0);
+}
+
+template <typename T, bool PACKED>
 __global__ __launch_bounds__(GEMM_THREADS) void conv_dx_kernel(ConvDxArgs p) {
   constexpr int BK = GemmT<T>::BK, KG = GemmT<T>::KG, NV = GemmT<T>::NV, KQ = GemmT<T>::KQ;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][GEMM_TILE_BYTES];
@@ -272,6 +295,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv_dx_kernel(ConvDxArgs p) {
   const int khkw = p.kh * p.kw, kjkj = p.KJ * p.KJ;
   const int64_t HoWo = (int64_t)p.Ho * p.Wo;
   const T* Wt = reinterpret_cast<const T*>(p.Wt) + (int64_t)b * p.Co * p.Ci * khkw;
+  const T* Wpk = PACKED ? reinterpret_cast<const T*>(p.Wp) + ((int64_t)b * gridDim.y + cls) * p.Ci * (int64_t)p.K : nullptr;
   const T* dyb = reinterpret_cast<const T*>(p.dY) + ((int64_t)nimg * p.B + b) * p.Co * HoWo;
 
   f32x16_t acc[2][2];
@@ -287,12 +311,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv_dx_kernel(ConvDxArgs p) {
   int qy[NV], qx[NV];
 #pragma unroll
   for (int e = 0; e < NV; ++e) p.d_wqm.divmod(n0 + ng * NV + e, qy[e], qx[e]);
+  // this thread's pixels sit side by side in one row of the class grid (bf16: four of them, read as one 8-byte piece)
+  const bool row4 = sizeof(T) == 2 && p.Wqm % NV == 0 && qy[0] < Hq && qx[0] + NV <= Wq;
 
   uint4 qa[2];
   uint2 qb[4];
   auto issue = [&](int tt) {
     const int k0 = tt * BK;
-    {
+    if (PACKED) {
+      const int k = k0 + ga * KG;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int m = m0 + ra + 64 * h;
+        qa[h] = (m < p.M && k + KG <= p.K) ? *reinterpret_cast<const uint4*>(Wpk + (int64_t)m * p.K + k) : make_uint4(0, 0, 0, 0);
+      }
+    } else {
       const int k = k0 + ga * KG;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
@@ -318,6 +351,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void conv_dx_kernel(ConvDxArgs p) {
       p.d_kjkj.divmod(k, o, r);
       p.d_kj.divmod(r, jy, jx);
       const bool tap_ok = k < p.K && ry + p.stride * jy < p.kh && rx + p.stride * jx < p.kw;
+      const int y0 = qy[0] - jy + cy, x0 = qx[0] - jx + cx;
+      if (row4 && tap_ok && (unsigned)y0 < (unsigned)p.Ho && x0 >= 0 && x0 + NV <= p.Wo) {
+        // four neighbouring dY values of one row; the address is only element-aligned
+        __builtin_memcpy(&qb[j], dyb + ((int64_t)o * p.Ho + y0) * p.Wo + x0, sizeof(uint2));
+        continue;
+      }
       T tmp[NV];
 #pragma unroll
       for (int e = 0; e < NV; ++e) {
@@ -827,6 +866,16 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   return launch_conv<CONV_FWD>(a, dtype, (unsigned)(B * Nb), as_stream(stream));
 }
 
+// Regrouped weights of the implicit data gradient (optional: the kernel gathers single taps without them).
+static size_t dx_pack_bytes(int B, int Ci, int Co, int kh, int kw, int stride, int dtype, ConvGeom g) {
+  const bool implicit_dx = (int64_t)g.Ho * g.Wo >= 256 && Ci >= 32;
+  const int kmax = kh > kw ? kh : kw, KJ = (kmax + stride - 1) / stride;
+  const int64_t K = (int64_t)Co * KJ * KJ;
+  const int kg = 16 / (int)dtype_size(dtype);
+  if (!implicit_dx || K % kg != 0 || K > 0x7fffffffLL) return 0;
+  return (size_t)B * stride * stride * Ci * K * dtype_size(dtype);
+}
+
 static size_t implicit_bwd_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad,
                                  int dtype, ConvGeom g) {
   ConvArgs a = base_args(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, g);
@@ -854,7 +903,9 @@ size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, in
   Lowered L;
   if (!lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L)) return imp;
   const size_t low = L.dcol_bytes + L.dyp_bytes + L.part_bytes;
-  return low > imp ? low : imp;
+  const size_t base = low > imp ? low : imp;
+  const size_t pk = dx_pack_bytes(B, Ci, Co, kh, kw, stride, dtype, g);
+  return pk ? align256(base) + pk : base;      // regrouped weights behind everything else
 }
 
 int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype,
@@ -943,8 +994,26 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
     a.d_kj = FastDiv::make(a.KJ); a.d_kjkj = FastDiv::make(a.KJ * a.KJ);
     a.d_wqm = FastDiv::make(a.Wqm); a.d_s = FastDiv::make(stride);
     dim3 grid((unsigned)(((a.M + GEMM_BM - 1) / GEMM_BM) * a.tiles_n), (unsigned)(stride * stride), (unsigned)(B * Nb));
-    if (dtype == HFTA_BF16) hipLaunchKernelGGL(conv_dx_kernel<bf16_raw>, grid, dim3(GEMM_THREADS), 0, st, a);
-    else hipLaunchKernelGGL(conv_dx_kernel<float>, grid, dim3(GEMM_THREADS), 0, st, a);
+    // regrouped weights live at the end of a full-size workspace; a smaller workspace selects the gathering variant
+    const size_t pk = dx_pack_bytes(B, Ci, Co, kh, kw, stride, dtype, g);
+    const size_t full = hfta_conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype);
+    if (pk && workspace && ws_bytes >= full && reinterpret_cast<uintptr_t>(workspace) % 256 == 0) {
+      unsigned char* wp = reinterpret_cast<unsigned char*>(workspace) + (full - pk);
+      a.Wp = wp;
+      const int64_t count = (int64_t)(pk / dtype_size(dtype));
+      dim3 pg((unsigned)((count + 255) / 256));
+      if (dtype == HFTA_BF16) {
+        hipLaunchKernelGGL(conv_dx_pack_w_kernel<bf16_raw>, pg, dim3(256), 0, st, a, reinterpret_cast<bf16_raw*>(wp), count);
+        hipLaunchKernelGGL((conv_dx_kernel<bf16_raw, true>), grid, dim3(GEMM_THREADS), 0, st, a);
+      } else {
+        hipLaunchKernelGGL(conv_dx_pack_w_kernel<float>, pg, dim3(256), 0, st, a, reinterpret_cast<float*>(wp), count);
+        hipLaunchKernelGGL((conv_dx_kernel<float, true>), grid, dim3(GEMM_THREADS), 0, st, a);
+      }
+    } else if (dtype == HFTA_BF16) {
+      hipLaunchKernelGGL((conv_dx_kernel<bf16_raw, false>), grid, dim3(GEMM_THREADS), 0, st, a);
+    } else {
+      hipLaunchKernelGGL((conv_dx_kernel<float, false>), grid, dim3(GEMM_THREADS), 0, st, a);
+    }
     if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   }
   if (dW) {

@@ -501,6 +501,9 @@ CONV_CASES = [
     (2, 4, 64, 1, 4, 4, 1, 0),      # last discriminator layer: 4x4 -> 1x1
     (2, 2, 6, 9, 9, 3, 1, 1),       # generic 3x3
     (1, 1, 8, 8, 10, 1, 1, 0),      # k = 1
+    (2, 2, 32, 24, 32, 4, 2, 1),    # data gradient on the parity-class kernel (16x16 outputs, >= 32 channels); regrouped weights
+    (1, 2, 40, 10, 34, 4, 2, 1),    # the same with a 17-wide class grid (no 4-pixel pieces)
+    (1, 2, 32, 9, 32, 4, 2, 1),     # the same with K = 36: weights gathered tap by tap
 ]
 
 
