@@ -156,6 +156,70 @@ __global__ __launch_bounds__(256) void xent_rows_kernel(const T* __restrict__ lo
   if (t == 0) rowloss[row] = lse - Elem<T>::load(z + lab);
 }
 
+// Rows of at most 256 * NV sixteen-byte pieces (8192 bf16 / 4096 fp32 classes at NV = 4): the row
+// sits in registers, so it is read once, each exponential is taken once, and the gradient leaves
+// in 16-byte pieces.  Same sums as xent_rows_kernel up to fp32 summation order.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void xent_rows_reg_kernel(const T* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                            float* __restrict__ rowloss, T* __restrict__ dlogits, int R, int K) {
+  constexpr int EPV = 16 / (int)sizeof(T);
+  __shared__ float sh[4];
+  const int r = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+  const int64_t row = (int64_t)b * R + r;
+  const uint4* z = reinterpret_cast<const uint4*>(logits + row * K);
+  uint4* dz = reinterpret_cast<uint4*>(dlogits + row * K);
+  const int nvec = K / EPV;
+  float x[NV][EPV];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int c = t + 256 * j;
+    const uint4 v = c < nvec ? z[c] : make_uint4(0, 0, 0, 0);
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { x[j][2 * i] = __uint_as_float(w[i] << 16); x[j][2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+    } else {
+      x[j][0] = __uint_as_float(v.x); x[j][1] = __uint_as_float(v.y); x[j][2] = __uint_as_float(v.z); x[j][3] = __uint_as_float(v.w);
+    }
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) mx = c < nvec ? fmaxf(mx, x[j][e]) : mx;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if ((t & 63) == 0) sh[t >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+  float se = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) {
+      x[j][e] = t + 256 * j < nvec ? __expf(x[j][e] - mx) : 0.f;     // from here on x holds exp(z - max)
+      se += x[j][e];
+    }
+  se = wave_sum(se);
+  __syncthreads();
+  if ((t & 63) == 0) sh[t >> 6] = se;
+  __syncthreads();
+  se = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+  const int lab = labels[row];
+  const float invR = 1.f / (float)R, inv_se = 1.f / se;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int c = t + 256 * j;
+    if (c >= nvec) continue;
+    float g[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) g[e] = (x[j][e] * inv_se - (c * EPV + e == lab ? 1.f : 0.f)) * invR;
+    if constexpr (sizeof(T) == 2)
+      dz[c] = make_uint4(pack_bf16x2(g[0], g[1]), pack_bf16x2(g[2], g[3]), pack_bf16x2(g[4], g[5]), pack_bf16x2(g[6], g[7]));
+    else
+      dz[c] = make_uint4(__float_as_uint(g[0]), __float_as_uint(g[1]), __float_as_uint(g[2]), __float_as_uint(g[3]));
+  }
+  if (t == 0) rowloss[row] = mx + logf(se) - Elem<T>::load(logits + row * K + lab);
+}
+
 __global__ __launch_bounds__(256) void xent_rows_reduce_kernel(const float* __restrict__ rowloss, float* __restrict__ loss, int R) {
   __shared__ float sh[4];
   const float* src = rowloss + (int64_t)blockIdx.x * R;
@@ -321,7 +385,16 @@ int hfta_softmax_xent_rows(int B, int R, int K, int dtype, const void* logits, c
   if (!workspace || ws_bytes < hfta_softmax_xent_rows_workspace_bytes(B, R)) return HFTA_EWORKSPACE;
   hipStream_t st = as_stream(stream);
   dim3 grid((unsigned)R, (unsigned)B);
-  if (dtype == HFTA_BF16)
+  const int epv = 16 / (int)dtype_size(dtype);
+  const bool in_regs = K % epv == 0 && K / epv <= 256 * 4 && reinterpret_cast<uintptr_t>(logits) % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(dlogits) % 16 == 0;
+  if (in_regs && dtype == HFTA_BF16)
+    hipLaunchKernelGGL((xent_rows_reg_kernel<bf16_raw, 4>), grid, dim3(256), 0, st, (const bf16_raw*)logits, labels,
+                       (float*)workspace, (bf16_raw*)dlogits, R, K);
+  else if (in_regs)
+    hipLaunchKernelGGL((xent_rows_reg_kernel<float, 4>), grid, dim3(256), 0, st, (const float*)logits, labels,
+                       (float*)workspace, (float*)dlogits, R, K);
+  else if (dtype == HFTA_BF16)
     hipLaunchKernelGGL(xent_rows_kernel<bf16_raw>, grid, dim3(256), 0, st, (const bf16_raw*)logits, labels, (float*)workspace,
                        (bf16_raw*)dlogits, R, K);
   else
