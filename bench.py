@@ -105,6 +105,8 @@ def kernel_label(name, a):
         return "gemm_pf_kernel(fwd)" if a[4] == 1 else "gemm_kernel(fwd)"
     if name == "linear_bwd":           # the MLP array asks for dX, dW and dbias in separate calls
         B, M, Fx, Fy, dt = a[:5]
+        if a[8] is not None and a[9] is not None:      # one call for everything (the Transformer array)
+            return "linear_bwd: gemm(dX) + gemm(dW) + splitk_reduce_kernel + colsum_kernel"
         if a[8] is not None:
             return ("gemm_big_kernel" if dt == 1 and big_gemm(B, M, Fx, Fy) else "gemm_pf_kernel") + "(dX)"
         if a[9] is not None:
@@ -172,7 +174,8 @@ def algorithmic_flops(name, a):
         B, M, Fx, Fy = a[:4]
         if name == "linear_bwd" and a[8] is None and a[9] is None:
             return 0.0
-        return 2.0 * B * M * Fx * Fy
+        both = name == "linear_bwd" and a[8] is not None and a[9] is not None
+        return (4.0 if both else 2.0) * B * M * Fx * Fy
     if name in ("conv1x1_fwd", "conv1x1_bwd"):
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * Co * L
@@ -225,6 +228,8 @@ def algorithmic_bytes(name, a):
         return 2 * B * Nb * Ci * L * _es(dt) + B * Co * Ci * (_es(dt) + 4) + B * Nb * Co * (_es(dt) + 4 + _es(dt))
     if name == "linear_bwd":
         B, M, Fx, Fy, dt = a[:5]
+        if a[8] is not None and a[9] is not None:      # x, W, dy in; dx, dW (fp32), dbias out
+            return B * (2 * M * Fx + Fx * Fy + M * Fy) * _es(dt) + B * (Fx * Fy + Fy) * 4
         if a[8] is not None:
             return B * (M * Fy + Fx * Fy + M * Fx) * _es(dt)
         if a[9] is not None:
