@@ -71,65 +71,6 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
   }
 }
 
-// Register-resident variant: a 1024-thread workgroup holds its whole channel (up to
-// MAXC * 1024 chunks of four elements) in registers between the statistics and the normalisation,
-// so the channel crosses HBM exactly once in and once out.
-template <typename T, int MAXC>
-__global__ __launch_bounds__(1024) void bn_fwd_conv_reg_kernel(BnFwdArgs p) {
-  constexpr int NT = 1024;
-  typedef typename Vec<T, 4>::type V;
-  __shared__ float sh[NT / 64][2];
-  const int c = blockIdx.x, b = blockIdx.y;
-  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
-  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
-  const int chunks = p.L / 4;
-  const int total = p.Nb * chunks;
-  const float shift = Elem<T>::load(x);
-  V r[MAXC];
-  float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-  for (int j = 0; j < MAXC; ++j) {
-    const int i = threadIdx.x + j * NT;
-    if (i < total) {
-      const int n = i / chunks, ch = i - n * chunks;
-      r[j] = *reinterpret_cast<const V*>(x + n * p.xsn + ch * 4);
-      const T* e = reinterpret_cast<const T*>(&r[j]);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) { const float d = Elem<T>::to_f32(e[q]) - shift; s1 += d; s2 = fmaf(d, d, s2); }
-    }
-  }
-  block_sum2<NT / 64>(s1, s2, sh);
-  const float m = (float)p.Nb * (float)p.L;
-  const float dm = s1 / m;
-  const float mean = shift + dm;
-  float var = s2 / m - dm * dm;
-  var = var < 0.f ? 0.f : var;
-  const float invstd = 1.0f / sqrtf(var + p.eps);
-  const int k = b * p.C + c;
-  const float g = p.gamma[k], bt = p.beta[k];
-  if (threadIdx.x == 0) {
-    p.save_mean[k] = mean;
-    p.save_invstd[k] = invstd;
-    if (p.running_mean) {
-      const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
-      p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
-      p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < MAXC; ++j) {
-    const int i = threadIdx.x + j * NT;
-    if (i < total) {
-      const int n = i / chunks, ch = i - n * chunks;
-      const T* e = reinterpret_cast<const T*>(&r[j]);
-      float v[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) v[q] = apply_act(fmaf(g, (Elem<T>::to_f32(e[q]) - mean) * invstd, bt), p.act, p.slope);
-      store_vec<T, 4>(y + n * p.ysn + ch * 4, v);
-    }
-  }
-}
-
 // Linear layout [.., Nb, C] (channel stride 1, the fully connected head): a workgroup owns 64
 // channels x 16 sample lanes, so the loads of a column are spread over lanes instead of walking one
 // after the other through the memory latency; per-lane partial sums meet in LDS in a fixed order.
@@ -239,68 +180,6 @@ __global__ __launch_bounds__(NT) void bn_bwd_conv_kernel(BnBwdArgs p) {
   }
 }
 
-template <typename T, int MAXC>
-__global__ __launch_bounds__(1024) void bn_bwd_conv_reg_kernel(BnBwdArgs p) {
-  constexpr int NT = 1024;
-  typedef typename Vec<T, 4>::type V;
-  __shared__ float sh[NT / 64][2];
-  const int c = blockIdx.x, b = blockIdx.y, k = b * p.C + c;
-  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
-  const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + c * p.dysc;
-  T* dx = reinterpret_cast<T*>(p.dX) + b * p.dxsb + c * p.dxsc;
-  const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
-  const int chunks = p.L / 4;
-  const int total = p.Nb * chunks;
-  V rx[MAXC], rd[MAXC];
-  float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-  for (int j = 0; j < MAXC; ++j) {
-    const int i = threadIdx.x + j * NT;
-    if (i < total) {
-      const int n = i / chunks, ch = i - n * chunks;
-      rx[j] = *reinterpret_cast<const V*>(x + n * p.xsn + ch * 4);
-      rd[j] = *reinterpret_cast<const V*>(dy + n * p.dysn + ch * 4);
-      const T* ex = reinterpret_cast<const T*>(&rx[j]);
-      const T* ed = reinterpret_cast<const T*>(&rd[j]);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float xh = (Elem<T>::to_f32(ex[q]) - mean) * invstd;
-        const float gr = Elem<T>::to_f32(ed[q]) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
-        s1 += gr;
-        s2 = fmaf(gr, xh, s2);
-      }
-    }
-  }
-  block_sum2<NT / 64>(s1, s2, sh);
-  if (threadIdx.x == 0) { p.dbeta[k] = s1; p.dgamma[k] = s2; }
-  const float m = (float)p.Nb * (float)p.L;
-  const float mb = s1 / m, mg = s2 / m, sc = g * invstd;
-  float s3 = 0.f;
-#pragma unroll
-  for (int j = 0; j < MAXC; ++j) {
-    const int i = threadIdx.x + j * NT;
-    if (i < total) {
-      const int n = i / chunks, ch = i - n * chunks;
-      const T* ex = reinterpret_cast<const T*>(&rx[j]);
-      const T* ed = reinterpret_cast<const T*>(&rd[j]);
-      float v[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float xh = (Elem<T>::to_f32(ex[q]) - mean) * invstd;
-        const float gr = Elem<T>::to_f32(ed[q]) * act_grad(fmaf(g, xh, bt), p.act, p.slope);
-        v[q] = sc * (gr - mb - xh * mg);
-        s3 += Elem<T>::to_f32(Elem<T>::from_f32(v[q]));
-      }
-      store_vec<T, 4>(dx + n * p.dxsn + ch * 4, v);
-    }
-  }
-  if (p.dx_sum) {
-    float dummy = 0.f;
-    block_sum2<NT / 64>(s3, dummy, sh);
-    if (threadIdx.x == 0) p.dx_sum[k] = s3;
-  }
-}
-
 template <typename T>
 __global__ __launch_bounds__(BNL_C * BNL_N) void bn_bwd_linear_kernel(BnBwdArgs p) {
   __shared__ float red[BNL_N][BNL_C];
@@ -347,14 +226,6 @@ bool vec_ok(const void* p, const int64_t* s, int L, int dtype) {
   return L % 4 == 0 && reinterpret_cast<uintptr_t>(p) % bytes == 0 && s[0] % 4 == 0 && s[1] % 4 == 0 && s[2] % 4 == 0;
 }
 
-// The register-resident kernels cross HBM once per direction but serialise load, reduce and store
-// phases with one or two workgroups per compute unit; measured slower than the wide streaming
-// kernels at the PointNet shapes (1018 vs 774 us forward), so they are opt-in.
-bool reg_resident() {
-  static const char* env = getenv("HFTA_BN_REG");
-  return env && env[0] == '1';
-}
-
 int layout_kind(const int64_t* s, int L) {
   if (s[3] == 1) return 1;                 // conv family
   if (L == 1 && s[2] == 1) return 2;       // linear family
@@ -390,12 +261,6 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   dim3 grid((unsigned)C, (unsigned)B);
   const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
   const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
-  const int64_t nchunks = (int64_t)Nb * (L / 4);
-  if (v4 && big && nchunks <= 20 * 1024 && reg_resident()) {
-    if (dtype == HFTA_BF16) hipLaunchKernelGGL((bn_fwd_conv_reg_kernel<bf16_raw, 20>), grid, dim3(1024), 0, st, a);
-    else hipLaunchKernelGGL((bn_fwd_conv_reg_kernel<float, 20>), grid, dim3(1024), 0, st, a);
-    return launch_status();
-  }
 #define HFTA_BN_FWD(T, V) \
   do { if (big) hipLaunchKernelGGL((bn_fwd_conv_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a); \
        else hipLaunchKernelGGL((bn_fwd_conv_kernel<T, V, 256>), grid, dim3(256), 0, st, a); } while (0)
@@ -429,12 +294,6 @@ int hfta_bn_bwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   dim3 grid((unsigned)C, (unsigned)B);
   const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(dY, dys, L, dtype) && vec_ok(dX, dxs, L, dtype);
   const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
-  const int64_t nchunks = (int64_t)Nb * (L / 4);
-  if (v4 && big && reg_resident() && ((dtype == HFTA_BF16 && nchunks <= 20 * 1024) || (dtype == HFTA_F32 && nchunks <= 10 * 1024))) {
-    if (dtype == HFTA_BF16) hipLaunchKernelGGL((bn_bwd_conv_reg_kernel<bf16_raw, 20>), grid, dim3(1024), 0, st, a);
-    else hipLaunchKernelGGL((bn_bwd_conv_reg_kernel<float, 10>), grid, dim3(1024), 0, st, a);
-    return launch_status();
-  }
 #define HFTA_BN_BWD(T, V) \
   do { if (big) hipLaunchKernelGGL((bn_bwd_conv_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a); \
        else hipLaunchKernelGGL((bn_bwd_conv_kernel<T, V, 256>), grid, dim3(256), 0, st, a); } while (0)
