@@ -654,12 +654,8 @@ struct FbpArgs {
 // (max, first argmax) instead of a store.  RT = 64: 32 accumulators and 16 in-flight W registers
 // per lane (140 registers) and 36 KB of LDS, so three workgroups share a compute unit and cover each
 // other's phases (128-row tiles: 201 registers, two workgroups, 10 % slower).
-#ifndef FBP_RT
-#define FBP_RT 64
-#endif
-#ifndef FBP_OCC
-#define FBP_OCC 3
-#endif
+constexpr int FBP_RT = 64;     // rows of a W tile
+constexpr int FBP_OCC = 3;     // workgroups per compute unit the register budget is set for
 template <int KT, int RT>
 __global__ __launch_bounds__(GEMM_THREADS, FBP_OCC) void fbp_main_kernel(FbpArgs p) {
   constexpr int PITCH = KT * 2 + 16;
@@ -868,12 +864,12 @@ __global__ __launch_bounds__(GEMM_THREADS, FBP_OCC) void fbp_main_kernel(FbpArgs
 // ---- statistics from the moments; T = W XX kept for the backward operator --------------------------
 __global__ __launch_bounds__(128) void fbp_stats_kernel(FbpArgs p) {
   constexpr int CB = 8;
-  __shared__ float wrow[CB][128];
+  __shared__ double wrow[CB][128];                       // widened once: the loop below is bound by fp64 issue
   __shared__ double red[2][CB][2];
   const int c0 = blockIdx.x * CB, b = blockIdx.y, cj = threadIdx.x;
   for (int e = cj; e < CB * p.Ci; e += 128) {
     const int cc = e / p.Ci, k = e - cc * p.Ci;
-    wrow[cc][k] = c0 + cc < p.Co ? bf16_to_f32(p.W[((int64_t)b * p.Co + c0 + cc) * p.Ci + k]) : 0.f;
+    wrow[cc][k] = c0 + cc < p.Co ? (double)bf16_to_f32(p.W[((int64_t)b * p.Co + c0 + cc) * p.Ci + k]) : 0.0;
   }
   __syncthreads();
   const bool live = cj < p.Ci;
@@ -886,14 +882,14 @@ __global__ __launch_bounds__(128) void fbp_stats_kernel(FbpArgs p) {
     for (int ci = 0; ci < p.Ci; ++ci) {                  // Ci is a multiple of 8 (host)
       const double x = (double)XXb[(int64_t)ci * p.Ci + cj];
 #pragma unroll
-      for (int e = 0; e < CB; ++e) T[e] = fma((double)wrow[e][ci], x, T[e]);
+      for (int e = 0; e < CB; ++e) T[e] = fma(wrow[e][ci], x, T[e]);
     }
   }
   const double sxj = live ? (double)p.SX[(int64_t)b * p.Ci + cj] : 0.0;
 #pragma unroll
   for (int e = 0; e < CB; ++e) {
     if (live && c0 + e < p.Co) p.T[((int64_t)b * p.Co + c0 + e) * p.Ci + cj] = (float)T[e];
-    const double w = live ? (double)wrow[e][cj] : 0.0;
+    const double w = live ? wrow[e][cj] : 0.0;
     double q = T[e] * w, s1 = w * sxj;                   // terms of W_c XX W_c^T and of W_c SX
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) { q += __shfl_xor(q, o, 64); s1 += __shfl_xor(s1, o, 64); }
