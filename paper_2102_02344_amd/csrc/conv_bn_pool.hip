@@ -97,7 +97,7 @@ struct GramArgs {
   uint32_t x_extent;
 };
 
-__global__ __launch_bounds__(GEMM_THREADS) void gram_kernel(GramArgs p) {
+__global__ __launch_bounds__(GEMM_THREADS, 3) void gram_kernel(GramArgs p) {
   constexpr int GP = 64 * 2 + 16;                        // bytes per LDS row: 64 points + pad
   __shared__ __attribute__((aligned(16))) unsigned char smem[2][128 * GP];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;

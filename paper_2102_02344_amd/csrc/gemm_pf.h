@@ -91,7 +91,9 @@ template <bool V16> struct PfOperand<false, V16> {  // m/n-contiguous: 4(k) x 4(
 };
 
 template <bool A_KC, bool B_KC, typename OutT, bool V16, int PF>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_pf_kernel(GemmArgs p) {
+// three workgroups per compute unit: the register budget this asks for (<= 168) makes the compiler keep
+// the accumulators in ordinary registers (120-137 in all), 40 KB of LDS each; four spill
+__global__ __launch_bounds__(GEMM_THREADS, 3) void gemm_pf_kernel(GemmArgs p) {
   typedef bf16_raw T;
   constexpr int BK = GemmT<T>::BK;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2][2][GEMM_TILE_BYTES];
