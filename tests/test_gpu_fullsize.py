@@ -432,3 +432,32 @@ def test_t0_attention_full_size_sampled():
         rel_ok(f64(dQKV[b, n, :, h * d:(h + 1) * d]), ds @ k, TOL["bf16"], "dq")
         rel_ok(f64(dQKV[b, n, :, E + h * d:E + (h + 1) * d]), ds.T @ q, TOL["bf16"], "dk")
         rel_ok(f64(dQKV[b, n, :, 2 * E + h * d:2 * E + (h + 1) * d]), gp.T @ dc, TOL["bf16"], "dv")
+
+
+def test_c1_with_transform_subnetworks_full_size():
+    """Config 1 with both transform sub-networks at the benchmarked size.  With the last Linear of
+    each sub-network zero the matrices are identities, so loss and the main network's gradients must
+    equal the plain config 1 array bit for bit (same kernels, same inputs; the transformed tensors
+    are exact copies); the sub-networks still receive finite, nonzero gradients."""
+    from paper_2102_02344_amd.arrays import FusedPointNetCls, FusedPointNetClsT
+    ts = hi.PointNetTSpec(cls=hi.spec_c1())
+    inp = hi.pointnet_t_inputs(ts)
+    n = len(ts.tnet_fc)
+    for p in inp["params"]:
+        for k in hi.tnet_sizes(ts):
+            p[f"t{k}.fc{n}.w"][:] = 0
+            p[f"t{k}.fc{n}.b"][:] = 0
+    arr = FusedPointNetClsT(ts, inp)
+    print("full-size check: transform array, identity matrices", flush=True)
+    arr.forward_backward()
+    torch.cuda.synchronize()
+    plain = FusedPointNetCls(ts.cls, dict(inp, params=[{k: v for k, v in p.items() if not k.startswith("t")}
+                                                       for p in inp["params"]]))
+    plain.forward_backward()
+    torch.cuda.synchronize()
+    assert torch.equal(arr.loss, plain.loss) and bool(torch.isfinite(arr.loss).all())
+    for name, _ in plain.shapes:
+        assert torch.equal(arr.g(name), plain.g(name)), name
+    for k in hi.tnet_sizes(ts):
+        g = arr.g(f"t{k}.fc{n}.w")
+        assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0, k
