@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   if (q == 0 && i < count) out[i] = (sh[0][li] + sh[1][li]) + (sh[2][li] + sh[3][li]);
 }
 
-int gemm_big_launch(const GemmDesc& d, const GemmArgs& a, bool v16, dim3 grid, hipStream_t st);
+int gemm_big_launch(const GemmDesc& d, const GemmArgs& a, bool v16, bool n16, dim3 grid, hipStream_t st);
 
 static inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -187,7 +187,13 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
       b.tiles_per_seg = (d.K + 63) / 64;
       b.total_tiles = d.S * b.tiles_per_seg;
       dim3 grid((unsigned)(b.tiles_m * b.tiles_n), 1, (unsigned)(G * splits));
-      const int rc = gemm_big_launch(d, b, v16 || !(d.a_kc || d.b_kc), grid, st);
+      // operands contiguous along m / n: 16-byte pieces when every row start and the extent allow it
+      auto n16ok = [&](const void* q, int64_t ld, int64_t ss, int64_t s0, int64_t s1, bool kc, int extent) {
+        return kc || (aligned_to(q, 16) && ld % 8 == 0 && ss % 8 == 0 && s0 % 8 == 0 && s1 % 8 == 0 && extent % 8 == 0);
+      };
+      const bool n16 = n16ok(d.A, d.a_ld, d.a_ss, d.a_g0, d.a_g1, d.a_kc, d.M) &&
+                       n16ok(d.Bm, d.b_ld, d.b_ss, d.b_g0, d.b_g1, d.b_kc, d.N);
+      const int rc = gemm_big_launch(d, b, v16 || !(d.a_kc || d.b_kc), n16, grid, st);
       if (rc == HFTA_OK && splits > 1 && !d.keep_partials) return reduce_partials(d, G, splits, st);
       if (rc != HFTA_EUNSUPPORTED) return rc;
     }

@@ -138,55 +138,73 @@ template <bool V16> struct BigOpKc {
   }
 };
 
-// m/n-contiguous operand: [64 k][256 n] as 16 k-quads x 64 n-groups of 4(k) x 4(n) blocks; a
-// thread owns k-quads t%8 and t%8 + 8 of n-group t/8, transposed in registers on the way to LDS
-struct BigOpNc {
-  typedef uint2 Regs[2][4];
-  uint32_t off0;      // (4 * (t%8)) * ld * 2 + c * 2, or out of range when the columns are
+// m/n-contiguous operand kept in its natural layout in LDS ([64 k][256 n], 576-byte rows: the same
+// 36864 bytes as the k-major tile) and transposed by the LDS transpose read on the way into the
+// matrix-instruction fragments: no register shuffles, global loads and LDS stores of 16 bytes (N16)
+// or 8 bytes (rows only 8-byte aligned, e.g. 2500 points).  A thread owns chunk t%32 (8 columns) of
+// rows t/32 + 16h.
+constexpr int BIG_NPITCH = 256 * 2 + 64;
+static_assert(64 * BIG_NPITCH == BIG_TILE, "natural-layout tile must fit the k-major tile's bytes");
+template <bool N16> struct BigOpNt {
+  typedef uint4 Regs[4];
+  uint32_t off0, off1;    // byte offsets of the chunk's two 8-byte halves in row k = t/32, or out of range
   uint32_t ldb;
-  int kq4;
   __device__ __forceinline__ void init(int col0, int cols, int64_t ld, int t) {
-    kq4 = 4 * (t & 7);
     ldb = (uint32_t)(ld * 2);
-    const int c = col0 + (t >> 3) * 4;
-    off0 = c + 4 <= cols ? (uint32_t)kq4 * ldb + (uint32_t)c * 2u : PF_OOB;
+    const int c = col0 + (t & 31) * 8, kr = t >> 5;
+    off0 = c + 4 <= cols ? (uint32_t)kr * ldb + (uint32_t)c * 2u : PF_OOB;
+    off1 = c + 8 <= cols ? (uint32_t)kr * ldb + (uint32_t)c * 2u + 8u : PF_OOB;
   }
   __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K) const {
-    const uint32_t kb = (uint32_t)k0 * ldb;
+    const int kr = (int)(threadIdx.x >> 5);
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const bool ok = k0 + 32 * h + kq4 + j < K;
-        const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok ? off0 + kb + (uint32_t)(32 * h + j) * ldb : PF_OOB), 0, 0);
-        q[h][j] = make_uint2(v.x, v.y);
+    for (int h = 0; h < 4; ++h) {
+      const bool ok = k0 + kr + 16 * h < K;
+      const uint32_t kb = (uint32_t)(k0 + 16 * h) * ldb;
+      if (N16) {               // host side: columns a multiple of 8, so the halves are in or out together
+        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(ok && off1 != PF_OOB ? off0 + kb : PF_OOB), 0, 0);
+        q[h] = make_uint4(v.x, v.y, v.z, v.w);
+      } else {
+        const pf_u32x2 lo = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok && off0 != PF_OOB ? off0 + kb : PF_OOB), 0, 0);
+        const pf_u32x2 hi = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok && off1 != PF_OOB ? off1 + kb : PF_OOB), 0, 0);
+        q[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
       }
+    }
   }
   static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) {
-    const int ng = t >> 3;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int kq = h * 8 + (t & 7);
-      const uint32_t a0 = q[h][0].x, a1 = q[h][1].x, a2 = q[h][2].x, a3 = q[h][3].x;
-      const uint32_t b0 = q[h][0].y, b1 = q[h][1].y, b2 = q[h][2].y, b3 = q[h][3].y;
-      uint2 o[4];
-      o[0] = make_uint2((a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16));
-      o[1] = make_uint2((a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u));
-      o[2] = make_uint2((b0 & 0xffffu) | (b1 << 16), (b2 & 0xffffu) | (b3 << 16));
-      o[3] = make_uint2((b0 >> 16) | (b1 & 0xffff0000u), (b2 >> 16) | (b3 & 0xffff0000u));
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<uint2*>(tile + (ng * 4 + i) * BIG_PITCH + kq * 8) = o[i];
-    }
+    for (int h = 0; h < 4; ++h)
+      *reinterpret_cast<uint4*>(tile + ((t >> 5) + 16 * h) * BIG_NPITCH + (t & 31) * 16) = q[h];
   }
 };
 
-template <bool KC, bool V16> struct BigOp;
-template <bool V16> struct BigOp<true, V16> : BigOpKc<V16> {};
-template <bool V16> struct BigOp<false, V16> : BigOpNc {};
+template <bool KC, bool V16, bool N16> struct BigOp;
+template <bool V16, bool N16> struct BigOp<true, V16, N16> : BigOpKc<V16> {};
+template <bool V16, bool N16> struct BigOp<false, V16, N16> : BigOpNt<N16> {};
+
+// Fragment of the 32x32x16 matrix instruction for the 32 rows (columns of the natural tile) from
+// `base` and k-step s: lane l holds row base + l%32 and k = 16s + 8(l/32) + 0..7.
+typedef short big_v4s __attribute__((ext_vector_type(4)));
+template <bool KC>
+__device__ __forceinline__ bf16x8_t big_frag(const unsigned char* tile, int base, int s, int lane) {
+  if (KC) return *reinterpret_cast<const bf16x8_t*>(tile + (base + (lane & 31)) * BIG_PITCH + (lane >> 5) * 16 + s * 32);
+  // Transpose read: in every group of 16 lanes, lane r supplies the address of four neighbouring
+  // columns in one k-row, and lane i = 4a + c receives column c of the rows supplied by lanes
+  // a, a+4, a+8, a+12.  With lane r pointing at k-row r/4 and column quad r%4, lane i of the group
+  // ends up with column i of the group's 16 and four consecutive k.
+  const int r16 = lane & 15;
+  const unsigned char* a0 = tile + (16 * s + 8 * (lane >> 5) + (r16 >> 2)) * BIG_NPITCH +
+                            (base + 16 * ((lane >> 4) & 1) + 4 * (r16 & 3)) * 2;
+  typedef __attribute__((address_space(3))) big_v4s* lds_v4s;
+  const big_v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(a0));
+  const big_v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(a0 + 4 * BIG_NPITCH));
+  union { big_v4s h[2]; bf16x8_t v; } u;
+  u.h[0] = lo; u.h[1] = hi;
+  return u.v;
+}
 
 // COLB: bias per column n (the fused Linear's), else per row m or none.
-template <bool A_KC, bool B_KC, typename OutT, bool V16, bool COLB, int ACT>
+template <bool A_KC, bool B_KC, typename OutT, bool V16, bool COLB, int ACT, bool N16 = false>
 __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[BIG_SMEM];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -219,12 +237,12 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  BigOp<A_KC, V16> oa;
-  BigOp<B_KC, V16> ob;
+  BigOp<A_KC, V16, N16> oa;
+  BigOp<B_KC, V16, N16> ob;
   oa.init(m0, p.M, p.a_ld, t);
   ob.init(n0, p.N, p.b_ld, t);
-  typename BigOp<A_KC, V16>::Regs ra[BIG_PF];
-  typename BigOp<B_KC, V16>::Regs rb[BIG_PF];
+  typename BigOp<A_KC, V16, N16>::Regs ra[BIG_PF];
+  typename BigOp<B_KC, V16, N16>::Regs rb[BIG_PF];
   const int t_end = (int)((int64_t)p.total_tiles * (split + 1) / p.splits);
   auto issue = [&](int set, int tt) {
     const bool live = tt < t_end;
@@ -251,15 +269,15 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
     for (int d = 0; d < BIG_PF; ++d) {
       const int cur = base + d;
       issue(d, cur + BIG_PF);
-      const unsigned char* As = tileA(buf) + (wm * 128 + r) * BIG_PITCH + gsel * 16;
-      const unsigned char* Bs = tileB(buf) + (wn * 64 + r) * BIG_PITCH + gsel * 16;
+      const unsigned char* As = tileA(buf);
+      const unsigned char* Bs = tileB(buf);
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         bf16x8_t a[4], b[2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(As + i * 32 * BIG_PITCH + s * 32);
+        for (int i = 0; i < 4; ++i) a[i] = big_frag<A_KC>(As, wm * 128 + i * 32, s, lane);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(Bs + j * 32 * BIG_PITCH + s * 32);
+        for (int j = 0; j < 2; ++j) b[j] = big_frag<B_KC>(Bs, wn * 64 + j * 32, s, lane);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
