@@ -174,6 +174,13 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
     a.b_extent = (uint32_t)b_ext;
   }
 
+  // operands contiguous along m / n: 16-byte pieces when every row start and the extent allow it
+  auto n16ok = [&](const void* q, int64_t ld, int64_t ss, int64_t s0, int64_t s1, bool kc, int extent) {
+    return kc || (aligned_to(q, 16) && ld % 8 == 0 && ss % 8 == 0 && s0 % 8 == 0 && s1 % 8 == 0 && extent % 8 == 0);
+  };
+  const bool n16 = n16ok(d.A, d.a_ld, d.a_ss, d.a_g0, d.a_g1, d.a_kc, d.M) &&
+                   n16ok(d.Bm, d.b_ld, d.b_ss, d.b_g0, d.b_g1, d.b_kc, d.N);
+
   // Compute-bound problems (MLP-sized bf16 GEMMs) take the 256x256 kernel: it needs 16-byte
   // loadable operands, no split, a long reduction, and enough tiles to give every compute unit
   // at least one.
@@ -187,12 +194,6 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
       b.tiles_per_seg = (d.K + 63) / 64;
       b.total_tiles = d.S * b.tiles_per_seg;
       dim3 grid((unsigned)(b.tiles_m * b.tiles_n), 1, (unsigned)(G * splits));
-      // operands contiguous along m / n: 16-byte pieces when every row start and the extent allow it
-      auto n16ok = [&](const void* q, int64_t ld, int64_t ss, int64_t s0, int64_t s1, bool kc, int extent) {
-        return kc || (aligned_to(q, 16) && ld % 8 == 0 && ss % 8 == 0 && s0 % 8 == 0 && s1 % 8 == 0 && extent % 8 == 0);
-      };
-      const bool n16 = n16ok(d.A, d.a_ld, d.a_ss, d.a_g0, d.a_g1, d.a_kc, d.M) &&
-                       n16ok(d.Bm, d.b_ld, d.b_ss, d.b_g0, d.b_g1, d.b_kc, d.N);
       const int rc = gemm_big_launch(d, b, v16 || !(d.a_kc || d.b_kc), n16, grid, st);
       if (rc == HFTA_OK && splits > 1 && !d.keep_partials) return reduce_partials(d, G, splits, st);
       if (rc != HFTA_EUNSUPPORTED) return rc;
@@ -206,7 +207,7 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   // kernel (branch-free buffer loads, several k-tiles in flight).
   const bool pf = v16 || v8;
   if (pf) {
-    rc = gemm_pf_launch(d, a, v16, grid, st);
+    rc = gemm_pf_launch(d, a, v16, n16, grid, st);
   } else {
     rc = d.dtype == HFTA_BF16 ? launch_layout<bf16_raw>(d, a, grid, st) : launch_layout<float>(d, a, grid, st);
   }

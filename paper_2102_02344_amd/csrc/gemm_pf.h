@@ -65,32 +65,85 @@ template <bool V16> struct PfOperand<true, V16> {   // k-contiguous: rows t/4 an
   static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) { store_kc(tile, q, t); }
 };
 
-template <bool V16> struct PfOperand<false, V16> {  // m/n-contiguous: 4(k) x 4(n) block, k-quad t%8, n-group t/8
-  typedef uint2 Regs[4];
-  uint32_t off[4];
+// m/n-contiguous operand: kept in its natural layout in LDS ([32 k][128 n], 320-byte rows = the k-major
+// tile's 10240 bytes) and transposed by the LDS transpose read on the way into the matrix-instruction
+// fragments.  A thread owns chunk t%16 (8 columns) of k-rows t/16 and t/16 + 16; N16: the chunk is one
+// 16-byte piece (row starts 16-byte aligned, columns a multiple of 8), else two 8-byte pieces.
+constexpr int PF_NPITCH = 128 * 2 + 64;
+static_assert(32 * PF_NPITCH == GEMM_TILE_BYTES, "natural-layout tile must fit the k-major tile's bytes");
+template <bool N16> struct PfOperandNt {
+  typedef uint4 Regs[2];
+  uint32_t off0, off1;
   uint32_t ldb;
-  int kq4;
   __device__ __forceinline__ void init(int col0, int cols, int64_t ld, int t) {
-    kq4 = 4 * (t % 8);
     ldb = (uint32_t)(ld * 2);
-    const int c = col0 + (t / 8) * 4;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      off[j] = c + 4 <= cols ? (uint32_t)(kq4 + j) * ldb + (uint32_t)c * 2u : PF_OOB;
+    const int c = col0 + (t & 15) * 8, kr = t >> 4;
+    off0 = c + 4 <= cols ? (uint32_t)kr * ldb + (uint32_t)c * 2u : PF_OOB;
+    off1 = c + 8 <= cols ? (uint32_t)kr * ldb + (uint32_t)c * 2u + 8u : PF_OOB;
   }
   __device__ __forceinline__ void load(Regs& q, __amdgpu_buffer_rsrc_t rs, int k0, int K) const {
-    const uint32_t kb = (uint32_t)k0 * ldb;
+    const int kr = (int)(threadIdx.x >> 4);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bool ok = k0 + kq4 + j < K;
-      const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok ? off[j] + kb : PF_OOB), 0, 0);
-      q[j] = make_uint2(v.x, v.y);
+    for (int h = 0; h < 2; ++h) {
+      const bool ok = k0 + kr + 16 * h < K;
+      const uint32_t kb = (uint32_t)(k0 + 16 * h) * ldb;
+      if (N16) {
+        const pf_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(ok && off1 != PF_OOB ? off0 + kb : PF_OOB), 0, 0);
+        q[h] = make_uint4(v.x, v.y, v.z, v.w);
+      } else {
+        const pf_u32x2 lo = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok && off0 != PF_OOB ? off0 + kb : PF_OOB), 0, 0);
+        const pf_u32x2 hi = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(ok && off1 != PF_OOB ? off1 + kb : PF_OOB), 0, 0);
+        q[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
     }
   }
-  static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) { store_nc_bf16(tile, q, t); }
+  static __device__ __forceinline__ void store(unsigned char* tile, const Regs& q, int t) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      *reinterpret_cast<uint4*>(tile + ((t >> 4) + 16 * h) * PF_NPITCH + (t & 15) * 16) = q[h];
+  }
 };
+template <bool V16> struct PfOperand<false, V16> : PfOperandNt<V16> {};   // for this operand kind V16 means N16
 
-template <bool A_KC, bool B_KC, typename OutT, bool V16, int PF>
+// Fragment for the 32 rows (columns of a natural-layout tile) from `base`, k-step s of the 32-deep tile:
+// lane l holds row base + l%32 and k = 16s + 8(l/32) + 0..7.  Transpose read: in every group of 16
+// lanes, lane r supplies the address of four neighbouring columns in one k-row and lane i = 4a + c
+// receives column c of the rows supplied by lanes a, a+4, a+8, a+12; with lane r on k-row r/4 and
+// column quad r%4, lane i ends up with column i of the group's 16 and four consecutive k.
+typedef short pf_v4s __attribute__((ext_vector_type(4)));
+template <bool KC>
+__device__ __forceinline__ bf16x8_t pf_frag(const unsigned char* tile, int base, int s, int lane) {
+  if (KC) return *reinterpret_cast<const bf16x8_t*>(tile + (base + (lane & 31)) * GEMM_PITCH + (2 * s + (lane >> 5)) * 16);
+  const int r16 = lane & 15;
+  const unsigned char* a0 = tile + (16 * s + 8 * (lane >> 5) + (r16 >> 2)) * PF_NPITCH +
+                            (base + 16 * ((lane >> 4) & 1) + 4 * (r16 & 3)) * 2;
+  typedef __attribute__((address_space(3))) pf_v4s* lds_v4s;
+  union { pf_v4s h[2]; bf16x8_t v; } u;
+  u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(a0));
+  u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(a0 + 4 * PF_NPITCH));
+  return u.v;
+}
+
+template <bool A_KC, bool B_KC>
+__device__ __forceinline__ void pf_mma_tile(f32x16_t (&acc)[2][2], const unsigned char* As, const unsigned char* Bs,
+                                            int wm, int wn, int lane) {
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    bf16x8_t a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      a[i] = pf_frag<A_KC>(As, wm * 64 + i * 32, s, lane);
+      b[i] = pf_frag<B_KC>(Bs, wn * 64 + i * 32, s, lane);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+  }
+}
+
+template <bool A_KC, bool B_KC, typename OutT, bool V16, int PF, bool N16 = false>
 // three workgroups per compute unit: the register budget this asks for (<= 168) makes the compiler keep
 // the accumulators in ordinary registers (120-137 in all), 40 KB of LDS each; four spill
 __global__ __launch_bounds__(GEMM_THREADS, 3) void gemm_pf_kernel(GemmArgs p) {
@@ -129,12 +182,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 3) void gemm_pf_kernel(GemmArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  PfOperand<A_KC, V16> oa;
-  PfOperand<B_KC, V16> ob;
+  PfOperand<A_KC, A_KC ? V16 : N16> oa;
+  PfOperand<B_KC, B_KC ? V16 : N16> ob;
   oa.init(m0, p.M, p.a_ld, t);
   ob.init(n0, p.N, p.b_ld, t);
-  typename PfOperand<A_KC, V16>::Regs ra[PF];
-  typename PfOperand<B_KC, V16>::Regs rb[PF];
+  typename PfOperand<A_KC, A_KC ? V16 : N16>::Regs ra[PF];
+  typename PfOperand<B_KC, B_KC ? V16 : N16>::Regs rb[PF];
 
   auto issue = [&](int set, int tt) {
     const bool live = tt < t_end;
@@ -159,7 +212,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 3) void gemm_pf_kernel(GemmArgs p) {
       for (int d = 0; d < PF; ++d) {
         const int cur = base + d;          // tile in LDS buffer `buf`; it came through register set d
         issue(d, cur + PF);                // set d is free again; beyond the end: zeros, no traffic
-        mma_tile<T>(acc, smem[buf][0], smem[buf][1], wm, wn, lane);
+        pf_mma_tile<A_KC, B_KC>(acc, smem[buf][0], smem[buf][1], wm, wn, lane);
         if (cur + 1 >= t_end) { done = true; break; }
         oa.store(smem[buf ^ 1][0], ra[(d + 1) % PF], t);
         ob.store(smem[buf ^ 1][1], rb[(d + 1) % PF], t);
@@ -182,6 +235,6 @@ __global__ __launch_bounds__(GEMM_THREADS, 3) void gemm_pf_kernel(GemmArgs p) {
   store_tile<OutT, T, sizeof(OutT) == 2>(acc, &smem[0][0][0], Cb, p.c_ld, p.M, p.N, m0, n0, bias, p.bias_mode, p.act, p.slope, p.c_vec, t, p.c_seg, p.c_seg_stride);
 }
 
-int gemm_pf_launch(const GemmDesc& d, const GemmArgs& a, bool v16, dim3 grid, hipStream_t st);
+int gemm_pf_launch(const GemmDesc& d, const GemmArgs& a, bool v16, bool n16, dim3 grid, hipStream_t st);
 
 }  // namespace hfta
