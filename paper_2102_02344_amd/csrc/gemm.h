@@ -68,6 +68,7 @@ struct GemmArgs {
   int bias_mode, act;
   float slope;
   uint32_t a_extent, b_extent;   // bytes from an operand slice's first to one past its last element
+  uint32_t c_extent;             // same for one output slice, or 0 when it does not fit 31 bits
   int c_seg;
   int64_t c_seg_stride;
 };

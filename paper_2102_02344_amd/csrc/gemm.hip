@@ -173,6 +173,12 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
     a.a_extent = (uint32_t)a_ext;
     a.b_extent = (uint32_t)b_ext;
   }
+  {
+    const int64_t last = d.N - 1;
+    const int64_t c_cols = d.c_seg > 0 ? (last / d.c_seg) * d.c_seg_stride + last % d.c_seg + 1 : (int64_t)d.N;
+    const int64_t c_ext = ((int64_t)(d.M - 1) * d.c_ld + c_cols) * oes;
+    a.c_extent = c_ext > 0 && c_ext < (int64_t)1 << 31 ? (uint32_t)c_ext : 0u;
+  }
 
   // operands contiguous along m / n: 16-byte pieces when every row start and the extent allow it
   auto n16ok = [&](const void* q, int64_t ld, int64_t ss, int64_t s0, int64_t s1, bool kc, int extent) {

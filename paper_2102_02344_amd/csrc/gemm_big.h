@@ -30,7 +30,7 @@ constexpr int BIG_PF = 2;                                // k-tiles in flight in
 // Epilogue kinds.  SEL: y = max(x, 0) + neg_slope * min(x, 0) -- identity (1), ReLU (0) and
 // LeakyReLU (slope) without a branch.  GELU here is x * Phi(x) with erf from the Abramowitz-Stegun
 // 7.1.26 rational form (|error| < 1.5e-7, far below bf16 resolution), TANH the library's.
-enum { BIG_SEL = 0, BIG_TANH = 1, BIG_GELU = 2 };
+enum { BIG_SEL = 0, BIG_TANH = 1, BIG_GELU = 2, BIG_NONE = 3 };
 
 __device__ __forceinline__ float gelu_as(float x) {
   const float z = fabsf(x) * 0.70710678118654752f;
@@ -48,6 +48,7 @@ __device__ __forceinline__ float gelu_as(float x) {
 
 template <int ACT>
 __device__ __forceinline__ float big_act(float x, float neg_slope) {
+  if (ACT == BIG_NONE) return x;
   if (ACT == BIG_SEL) return fmaf(neg_slope, fminf(x, 0.f), fmaxf(x, 0.f));
   if (ACT == BIG_TANH) return tanhf(x);
   return gelu_as(x);
@@ -361,6 +362,271 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
     __syncthreads();
     big_store_rows<OutT, BIG_THREADS>(smem, Cb, c_ld, p.M, p.N, m0 + pass * RP, n0, c_vec, t, c_seg, p.c_seg_stride);
     if (pass + 1 < 256 / RP) __syncthreads();
+  }
+}
+
+// ---- persistent variant ------------------------------------------------------------------
+// One workgroup per compute unit walks the output tiles lin = blockIdx.x, blockIdx.x + gridDim.x, ...
+// of the same XCD-aware numbering.  With one workgroup per compute unit nothing overlaps a tile's
+// launch, first loads, bias fetch and epilogue, which together cost as much as nine k-tiles; here
+// the loader runs two k-tiles ahead across tile boundaries, so the next tile's first two k-tiles
+// (and this tile's bias) are in flight while the last two k-tiles are multiplied and the epilogue
+// runs.  Rows of k-tiles come in pairs (an odd count multiplies one all-zero k-tile), which keeps
+// the register sets' roles fixed at a tile boundary.  Stores are raw buffer stores (a piece outside
+// the matrix gets an out-of-range offset and is dropped), so the epilogue is straight-line code and
+// the wait for the prefetched loads does not have to cover the stores behind them.  The epilogue
+// is vector-ALU bound (two waves per SIMD, nothing to overlap it), so no activation (BIG_NONE) is a
+// compile-time case of its own rather than a select with slope 1.
+// Host side guarantees: 16-byte loadable operands, 16-byte aligned output rows, N a multiple of the
+// store piece, output slice below 2 GiB.
+template <typename OutT>
+__device__ __forceinline__ void bigp_store_rows(const unsigned char* smem, __amdgpu_buffer_rsrc_t rc, uint32_t c_ldb,
+                                                int M, int mbase, uint32_t col_byte, int t) {
+  constexpr int ES = sizeof(OutT);
+  constexpr int RP = ES == 2 ? 128 : 64;
+  constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
+  constexpr int EPV = 16 / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
+  const int r0 = t / PPR, c = t % PPR;
+  constexpr int NIT = RP / RPI;                          // 8 pieces per thread, read two at a time
+#pragma unroll
+  for (int h = 0; h < NIT; h += 2) {
+    uint4 v[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it)
+      v[it] = *reinterpret_cast<const uint4*>(smem + (r0 + (h + it) * RPI) * PITCH + c * 16);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int m = mbase + r0 + (h + it) * RPI;
+      const uint32_t off = (m < M && col_byte != PF_OOB) ? (uint32_t)m * c_ldb + col_byte : PF_OOB;
+      pf_u32x4 w; w.x = v[it].x; w.y = v[it].y; w.z = v[it].z; w.w = v[it].w;
+      __builtin_amdgcn_raw_buffer_store_b128(w, rc, (int)off, 0, 0);
+    }
+  }
+}
+
+struct BigCoord { int m0, n0, g0, g1, split, g, t_begin, t_end; };
+
+template <bool A_KC, bool B_KC, typename OutT, bool COLB, int ACT>
+__global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int vgx, int vtotal) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[BIG_SMEM];
+  __shared__ uint2 sbias[64];                            // this tile's 256 column biases (an object of its own:
+                                                         // its reads need not wait for the staging writes)
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  constexpr int ES = sizeof(OutT);
+  constexpr int RP = ES == 2 ? 128 : 64;
+  constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
+  constexpr int EPV = 16 / ES;
+  const bool to_partial = ES == 4 && p.splits > 1;
+  const int groups = vtotal / vgx / p.splits;            // G0 * G1
+
+  // tile lin of the virtual (tiles, 1, groups * splits) grid, renumbered as in gemm_big_kernel
+  auto coord = [&](int lin) {
+    int bx, bz;
+    const int per = vtotal >> 3;
+    const int l2 = lin < (per << 3) ? (lin & 7) * per + (lin >> 3) : lin;
+    bz = l2 / vgx;
+    bx = l2 - bz * vgx;
+    BigCoord c;
+    c.m0 = (bx % p.tiles_m) * BIG_BM;
+    c.n0 = (bx / p.tiles_m) * BIG_BN;
+    c.split = bz % p.splits;
+    c.g = bz / p.splits;
+    c.g0 = c.g / p.G1;
+    c.g1 = c.g % p.G1;
+    c.t_begin = (int)((int64_t)p.total_tiles * c.split / p.splits);
+    c.t_end = (int)((int64_t)p.total_tiles * (c.split + 1) / p.splits);
+    return c;
+  };
+
+  // loader state: the tile whose k-tiles are being fetched
+  BigOp<A_KC, true, true> oa;
+  BigOp<B_KC, true, true> ob;
+  typename BigOp<A_KC, true, true>::Regs ra[BIG_PF];
+  typename BigOp<B_KC, true, true>::Regs rb[BIG_PF];
+  const bf16_raw* Ab;
+  const bf16_raw* Bb;
+  int l_end;
+  auto aim = [&](const BigCoord& c, bool live) {
+    Ab = reinterpret_cast<const bf16_raw*>(p.A) + c.g0 * p.a_g0 + c.g1 * p.a_g1;
+    Bb = reinterpret_cast<const bf16_raw*>(p.Bm) + c.g0 * p.b_g0 + c.g1 * p.b_g1;
+    l_end = live ? c.t_end : 0;
+    oa.init(c.m0, p.M, p.a_ld, t);
+    ob.init(c.n0, p.N, p.b_ld, t);
+  };
+  auto issue = [&](int set, int tt) {
+    const bool live = tt < l_end;
+    const int Ke = live ? p.K : 0;      // a dead k-tile has no valid k: every offset out of range
+    const int tc = live ? tt : 0;
+    const int seg = tc / p.tiles_per_seg;
+    const int k0 = (tc - seg * p.tiles_per_seg) * BIG_BK;
+    oa.load(ra[set], pf_rsrc(Ab + seg * p.a_ss, p.a_extent), k0, Ke);
+    ob.load(rb[set], pf_rsrc(Bb + seg * p.b_ss, p.b_extent), k0, Ke);
+  };
+  auto tileA = [&](int buf) { return smem + buf * 2 * BIG_TILE; };
+  auto tileB = [&](int buf) { return smem + buf * 2 * BIG_TILE + BIG_TILE; };
+
+  f32x16_t acc[4][2];
+  auto multiply = [&](int buf) {
+    const unsigned char* As = tileA(buf);
+    const unsigned char* Bs = tileB(buf);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      bf16x8_t a[4], b[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = big_frag<A_KC>(As, wm * 128 + i * 32, s, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = big_frag<B_KC>(Bs, wn * 64 + j * 32, s, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  const int ml = lane & 31, nq = (lane >> 5) * 4;
+  const float neg_slope = p.slope;
+  BigCoord cur = coord(blockIdx.x);
+  aim(cur, true);
+  issue(0, cur.t_begin);
+  issue(1, cur.t_begin + 1);
+  oa.store(tileA(0), ra[0], t);
+  ob.store(tileB(0), rb[0], t);
+  __syncthreads();
+
+  // A pair multiplies the k-tile in LDS buffer 0 (its partner is in flight in register set 1), then
+  // the partner from buffer 1; the loads it issues are two k-tiles ahead, and in the last pair of a
+  // tile they belong to the next tile (or are dead after the last one).
+  for (int lin = blockIdx.x;;) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int pairs = (cur.t_end - cur.t_begin + 1) >> 1;
+    const int nlin = lin + (int)gridDim.x;
+    const bool more = nlin < vtotal;
+    BigCoord nxt = cur;
+    pf_u32x2 bcol;
+    bcol.x = 0u; bcol.y = 0u;
+    unsigned short bmp[4] = {0, 0, 0, 0};
+    int tt = cur.t_begin + 2;
+    for (int pr = 1;; ++pr, tt += 2) {
+      const bool last = pr >= pairs;
+      if (last) {
+        if (more) nxt = coord(nlin);
+        aim(nxt, more);
+        tt = nxt.t_begin;
+        // this tile's bias (the resource's extent does the bounds check: N is a multiple of 4 for a
+        // column bias, so an 8-byte piece is inside or outside as a whole; no bias = empty = zeros).
+        // The 256 column biases go through LDS: wave 0 fetches them here and parks them below.
+        const bf16_raw* bias = p.bias ? reinterpret_cast<const bf16_raw*>(p.bias) + cur.g0 * p.bias_g0 + cur.g1 * p.bias_g1 : nullptr;
+        if (COLB) {
+          const __amdgpu_buffer_rsrc_t rbias = pf_rsrc(bias, (uint32_t)p.N * 2u);
+          bcol = __builtin_amdgcn_raw_buffer_load_b64(rbias, (int)(t < 64 ? (uint32_t)(cur.n0 + 4 * t) * 2u : PF_OOB), 0, 0);
+        } else {
+          const __amdgpu_buffer_rsrc_t rbias = pf_rsrc(bias, bias ? (uint32_t)p.M * 2u : 0u);
+          const uint32_t mb = (uint32_t)(cur.m0 + wm * 128 + ml) * 2u;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            bmp[i] = __builtin_amdgcn_raw_buffer_load_b16(rbias, (int)(mb + (uint32_t)(i * 32) * 2u), 0, 0);
+        }
+      }
+      issue(0, tt);
+      multiply(0);
+      oa.store(tileA(1), ra[1], t);
+      ob.store(tileB(1), rb[1], t);
+      __syncthreads();
+      issue(1, tt + 1);
+      multiply(1);
+      if (last) break;
+      oa.store(tileA(0), ra[0], t);
+      ob.store(tileB(0), rb[0], t);
+      __syncthreads();
+    }
+    // (thread index rebuilt from the wave number in a scalar register and the lane count, so that
+    // it is not carried in a vector register through the k-loop)
+    const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    if (COLB && wave_s == 0) {
+      uint2 bv; bv.x = bcol.x; bv.y = bcol.y;
+      sbias[lane_e] = bv;
+    }
+    __syncthreads();
+
+    // epilogue (see gemm_big_kernel): lane l holds row l % 32 and columns 8*(v/4) + 4*(l/32) + v%4
+    {
+      OutT* Cb = to_partial
+          ? reinterpret_cast<OutT*>(p.partial) + ((int64_t)cur.split * groups + cur.g) * (int64_t)p.M * p.N
+          : reinterpret_cast<OutT*>(p.C) + cur.g0 * p.c_g0 + cur.g1 * p.c_g1;
+      const uint32_t c_ldb = (uint32_t)((to_partial ? (int64_t)p.N : p.c_ld) * ES);
+      const __amdgpu_buffer_rsrc_t rc = pf_rsrc(Cb, to_partial ? (uint32_t)((int64_t)p.M * p.N * 4) : p.c_extent);
+      // this thread's store column; computed here from opaque copies so that neither it nor the
+      // segment division's reciprocal is carried in registers through the k-loop
+      int tq = wave_s * 64 + lane_e, cs = p.c_seg;
+      asm volatile("" : "+v"(tq), "+s"(cs));
+      const int n = cur.n0 + (tq % (256 / EPV)) * EPV;
+      const uint32_t col_byte = n + EPV <= p.N
+          ? (uint32_t)((to_partial ? (int64_t)n : col_offset(n, cs, p.c_seg_stride)) * ES) : PF_OOB;
+      uint2 cbp[2][4];                                   // this lane's 32 column biases, packed
+      if (COLB) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) cbp[j][q] = sbias[(wn * 64 + j * 32 + 8 * q + nq) >> 2];
+      }
+#pragma unroll
+      for (int pass = 0; pass < 256 / RP; ++pass) {
+        if (wm == pass * RP / 128) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int row = i * 32;
+            if (row / RP != (pass * RP % 128) / RP) continue;
+            const int rl = row % RP + ml;
+            const float bm = COLB ? 0.f : __uint_as_float((uint32_t)bmp[i] << 16);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const int nl = wn * 64 + j * 32 + 8 * q + nq;
+                float cbv[4] = {bm, bm, bm, bm};
+                if (COLB) {
+                  uint2 cb = cbp[j][q];
+                  asm volatile("" : "+v"(cb.x), "+v"(cb.y));   // unpack at each use: 16 registers, not 32
+                  cbv[0] = __uint_as_float(cb.x << 16);
+                  cbv[1] = __uint_as_float(cb.x & 0xffff0000u);
+                  cbv[2] = __uint_as_float(cb.y << 16);
+                  cbv[3] = __uint_as_float(cb.y & 0xffff0000u);
+                }
+                float x[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = big_act<ACT>(acc[i][j][4 * q + e] + cbv[e], neg_slope);
+                unsigned char* dst = smem + rl * PITCH + nl * ES;
+                if (ES == 2) {
+                  uint2 o;
+                  o.x = pack_bf16x2(x[0], x[1]);
+                  o.y = pack_bf16x2(x[2], x[3]);
+                  *reinterpret_cast<uint2*>(dst) = o;
+                } else {
+                  *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+                }
+              }
+          }
+        }
+        __syncthreads();
+        bigp_store_rows<OutT>(smem, rc, c_ldb, p.M, cur.m0 + pass * RP, col_byte, t);
+        __syncthreads();
+      }
+    }
+    if (!more) break;
+    oa.store(tileA(0), ra[0], t);
+    ob.store(tileB(0), rb[0], t);
+    __syncthreads();
+    cur = nxt;
+    lin = nlin;
   }
 }
 

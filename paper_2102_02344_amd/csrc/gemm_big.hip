@@ -13,6 +13,39 @@ static void launch_big(const GemmArgs& a, bool n16, dim3 grid, hipStream_t st) {
     hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, OutT, true, COLB, ACT, false>), grid, dim3(BIG_THREADS), 0, st, a);
 }
 
+// Persistent form: as many workgroups as compute units (a multiple of 8, one per XCD slot), each
+// walking several output tiles.  Taken when a launch has more tiles than that, the epilogue is the
+// select kind, every operand loads in 16-byte pieces, and output rows take whole 16-byte stores.
+static int persistent_blocks() {
+  static const int n = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return 0;
+    return cus / 8 * 8;
+  }();
+  return n;
+}
+
+template <bool A_KC, bool B_KC, typename OutT, bool COLB>
+static void launch_bigp(const GemmArgs& a, bool ident, dim3 grid, int blocks, hipStream_t st) {
+  if (ident)
+    hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_NONE>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0, st, a,
+                       (int)grid.x, (int)(grid.x * grid.z));
+  else
+    hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_SEL>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0, st, a,
+                       (int)grid.x, (int)(grid.x * grid.z));
+}
+
+static bool persistent_ok(const GemmDesc& d, const GemmArgs& a, bool n16, bool sel, dim3 grid, int blocks) {
+  if (blocks < 8 || (int64_t)grid.x * grid.z <= blocks || !sel) return false;
+  if (!n16 && !(d.a_kc && d.b_kc)) return false;
+  const bool partial = a.splits > 1;
+  const int oes = (d.out_f32 || partial) ? 4 : 2;
+  if (d.N % (16 / oes) != 0) return false;
+  if (partial) return a.p_vec == 16 && (int64_t)d.M * d.N * 4 < (int64_t)1 << 31;
+  return a.c_vec == 16 && a.c_extent != 0;
+}
+
 // `a` must carry tile counts for 256x256 tiles and 64-element k-tiles and operand extents.
 // `v16`: k-contiguous operands are loadable in 16-byte pieces; otherwise (rows only 8-byte aligned,
 // e.g. 2500 points per sample) only the weight-gradient form (both operands k-contiguous, fp32
@@ -29,6 +62,24 @@ int gemm_big_launch(const GemmDesc& d, const GemmArgs& a0, bool v16, bool n16, d
     if (!(d.out_f32 && d.a_kc && d.b_kc) || colb || !sel) return HFTA_EUNSUPPORTED;
     hipLaunchKernelGGL((gemm_big_kernel<true, true, float, false, false, BIG_SEL>), grid, dim3(BIG_THREADS), 0, st, a);
     return launch_status();
+  }
+  const int blocks = persistent_blocks();
+  if (persistent_ok(d, a, n16, sel, grid, blocks)) {
+    const bool f32 = d.out_f32 || a.splits > 1;
+    const bool ident = d.act == HFTA_ACT_NONE;
+    if (f32 && !colb) {
+      if (d.a_kc && !d.b_kc) { launch_bigp<true, false, float, false>(a, ident, grid, blocks, st); return launch_status(); }
+      if (d.a_kc && d.b_kc) { launch_bigp<true, true, float, false>(a, ident, grid, blocks, st); return launch_status(); }
+      if (!d.a_kc && !d.b_kc) { launch_bigp<false, false, float, false>(a, ident, grid, blocks, st); return launch_status(); }
+    } else if (!f32) {
+      if (d.a_kc && !d.b_kc) {
+        if (colb) launch_bigp<true, false, bf16_raw, true>(a, ident, grid, blocks, st);
+        else launch_bigp<true, false, bf16_raw, false>(a, ident, grid, blocks, st);
+        return launch_status();
+      }
+      if (!colb && d.a_kc && d.b_kc) { launch_bigp<true, true, bf16_raw, false>(a, ident, grid, blocks, st); return launch_status(); }
+      if (!colb && !d.a_kc && !d.b_kc) { launch_bigp<false, false, bf16_raw, false>(a, ident, grid, blocks, st); return launch_status(); }
+    }
   }
   if (d.out_f32) {
     if (colb || !sel) return HFTA_EUNSUPPORTED;

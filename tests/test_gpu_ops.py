@@ -33,7 +33,9 @@ def f32_tol(dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,M,Fx,Fy", [(3, 300, 200, 260), (2, 5, 1024, 16), (1, 129, 7, 3), (4, 32, 256, 512),
                                         # many models, ragged 256x256 tiles: all three forms take the compute-bound kernel
-                                        (100, 320, 264, 200), (50, 260, 136, 300)])
+                                        (100, 320, 264, 200), (50, 260, 136, 300),
+                                        # more tiles than compute units, odd k-tile counts: the persistent form
+                                        (40, 520, 520, 520), (12, 1100, 264, 1032)])
 def test_linear_fwd_bwd(hb, dtype, B, M, Fx, Fy):
     print(f"linear {dtype} B={B} M={M} Fx={Fx} Fy={Fy}", flush=True)
     x = hi.normal(1, (B, M, Fx), dtype)
@@ -113,7 +115,9 @@ def test_linear_fwd_with_workspace(hb, dtype, B, M, Fx, Fy, act):
 @pytest.mark.parametrize("B,Nb,Ci,Co,L", [(3, 2, 70, 150, 300), (2, 3, 3, 64, 250), (2, 2, 128, 40, 129),
                                           (2, 4, 64, 64, 500), (2, 3, 3, 64, 1300), (3, 2, 4, 24, 132),
                                           (2, 2, 128, 64, 260), (2, 2, 256, 520, 260), (2, 2, 520, 256, 132),
-                                          (1, 2, 200, 512, 132)])
+                                          (1, 2, 200, 512, 132),
+                                          # more 256x256 tiles than compute units: the persistent GEMM form
+                                          (3, 32, 264, 520, 520)])
 def test_conv1x1_fwd_bwd(hb, dtype, B, Nb, Ci, Co, L):
     print(f"conv1x1 {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} L={L}", flush=True)
     x = hi.normal(11, (Nb, B * Ci, L), dtype)
