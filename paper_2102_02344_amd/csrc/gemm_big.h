@@ -379,23 +379,29 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
 // compile-time case of its own rather than a select with slope 1.
 // Host side guarantees: 16-byte loadable operands, 16-byte aligned output rows, N a multiple of the
 // store piece, output slice below 2 GiB.
+// rows staged per epilogue pass: the whole tile for 2-byte outputs (133 KB of the 144 KB the k-loop's
+// tiles leave free: every wave converts at the same time), a quarter of it for 4-byte outputs
+constexpr int BIGP_RP(int es) { return es == 2 ? 256 : 64; }
+static_assert(256 * BIG_EPI_PITCH <= BIG_SMEM && 64 * BIG_EPI_PITCH4 <= BIG_SMEM, "staging must fit the tile buffers");
+
 template <typename OutT>
 __device__ __forceinline__ void bigp_store_rows(const unsigned char* smem, __amdgpu_buffer_rsrc_t rc, uint32_t c_ldb,
                                                 int M, int mbase, uint32_t col_byte, int t) {
   constexpr int ES = sizeof(OutT);
-  constexpr int RP = ES == 2 ? 128 : 64;
+  constexpr int RP = BIGP_RP(ES);
   constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
   constexpr int EPV = 16 / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
   const int r0 = t / PPR, c = t % PPR;
-  constexpr int NIT = RP / RPI;                          // 8 pieces per thread, read two at a time
+  constexpr int NIT = RP / RPI;                          // pieces per thread, read NB at a time
+  constexpr int NB = ES == 2 ? 4 : 2;
 #pragma unroll
-  for (int h = 0; h < NIT; h += 2) {
-    uint4 v[2];
+  for (int h = 0; h < NIT; h += NB) {
+    uint4 v[NB];
 #pragma unroll
-    for (int it = 0; it < 2; ++it)
+    for (int it = 0; it < NB; ++it)
       v[it] = *reinterpret_cast<const uint4*>(smem + (r0 + (h + it) * RPI) * PITCH + c * 16);
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
+    for (int it = 0; it < NB; ++it) {
       const int m = mbase + r0 + (h + it) * RPI;
       const uint32_t off = (m < M && col_byte != PF_OOB) ? (uint32_t)m * c_ldb + col_byte : PF_OOB;
       pf_u32x4 w; w.x = v[it].x; w.y = v[it].y; w.z = v[it].z; w.w = v[it].w;
@@ -415,7 +421,7 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
   const int wm = wave >> 2, wn = wave & 3;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   constexpr int ES = sizeof(OutT);
-  constexpr int RP = ES == 2 ? 128 : 64;
+  constexpr int RP = BIGP_RP(ES);
   constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
   constexpr int EPV = 16 / ES;
   const bool to_partial = ES == 4 && p.splits > 1;
@@ -488,10 +494,42 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
 
   const int ml = lane & 31, nq = (lane >> 5) * 4;
   const float neg_slope = p.slope;
+  // The bias is the accumulators' initial value, so the epilogue (vector-ALU bound) does not add
+  // it.  Column biases of the tile about to start sit in `sbias` (wave 0 fetches the 256 of them);
+  // row biases in four registers per lane.  The resource's extent does the bounds check (N is a
+  // multiple of 4 for a column bias, so an 8-byte piece is inside or outside as a whole; no bias =
+  // empty extent = zeros).
+  unsigned short bmp[4] = {0, 0, 0, 0};
+  auto fetch_bias = [&](const BigCoord& c, pf_u32x2& bcol) {
+    const bf16_raw* bias = p.bias ? reinterpret_cast<const bf16_raw*>(p.bias) + c.g0 * p.bias_g0 + c.g1 * p.bias_g1 : nullptr;
+    if (COLB) {
+      const __amdgpu_buffer_rsrc_t rbias = pf_rsrc(bias, (uint32_t)p.N * 2u);
+      bcol = __builtin_amdgcn_raw_buffer_load_b64(rbias, (int)(t < 64 ? (uint32_t)(c.n0 + 4 * t) * 2u : PF_OOB), 0, 0);
+    } else {
+      const __amdgpu_buffer_rsrc_t rbias = pf_rsrc(bias, bias ? (uint32_t)p.M * 2u : 0u);
+      const uint32_t mb = (uint32_t)(c.m0 + wm * 128 + ml) * 2u;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        bmp[i] = __builtin_amdgcn_raw_buffer_load_b16(rbias, (int)(mb + (uint32_t)(i * 32) * 2u), 0, 0);
+    }
+  };
+  auto park_bias = [&](const pf_u32x2& bcol) {
+    if (COLB && wave_s == 0) {
+      uint2 bv; bv.x = bcol.x; bv.y = bcol.y;
+      sbias[(int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u))] = bv;
+    }
+  };
+
   BigCoord cur = coord(blockIdx.x);
   aim(cur, true);
   issue(0, cur.t_begin);
   issue(1, cur.t_begin + 1);
+  {
+    pf_u32x2 bcol;
+    bcol.x = 0u; bcol.y = 0u;
+    fetch_bias(cur, bcol);
+    park_bias(bcol);
+  }
   oa.store(tileA(0), ra[0], t);
   ob.store(tileB(0), rb[0], t);
   __syncthreads();
@@ -501,11 +539,23 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
   // tile they belong to the next tile (or are dead after the last one).
   for (int lin = blockIdx.x;;) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int q = 0; q < 4; ++q) {
+        float cbv[4];
+        if (COLB) {
+          const uint2 cb = sbias[(wn * 64 + j * 32 + 8 * q + nq) >> 2];
+          cbv[0] = __uint_as_float(cb.x << 16);
+          cbv[1] = __uint_as_float(cb.x & 0xffff0000u);
+          cbv[2] = __uint_as_float(cb.y << 16);
+          cbv[3] = __uint_as_float(cb.y & 0xffff0000u);
+        }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            acc[i][j][4 * q + e] = COLB ? cbv[e] : __uint_as_float((uint32_t)bmp[i] << 16);
+      }
 
     const int pairs = (cur.t_end - cur.t_begin + 1) >> 1;
     const int nlin = lin + (int)gridDim.x;
@@ -513,7 +563,6 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
     BigCoord nxt = cur;
     pf_u32x2 bcol;
     bcol.x = 0u; bcol.y = 0u;
-    unsigned short bmp[4] = {0, 0, 0, 0};
     int tt = cur.t_begin + 2;
     for (int pr = 1;; ++pr, tt += 2) {
       const bool last = pr >= pairs;
@@ -521,20 +570,7 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
         if (more) nxt = coord(nlin);
         aim(nxt, more);
         tt = nxt.t_begin;
-        // this tile's bias (the resource's extent does the bounds check: N is a multiple of 4 for a
-        // column bias, so an 8-byte piece is inside or outside as a whole; no bias = empty = zeros).
-        // The 256 column biases go through LDS: wave 0 fetches them here and parks them below.
-        const bf16_raw* bias = p.bias ? reinterpret_cast<const bf16_raw*>(p.bias) + cur.g0 * p.bias_g0 + cur.g1 * p.bias_g1 : nullptr;
-        if (COLB) {
-          const __amdgpu_buffer_rsrc_t rbias = pf_rsrc(bias, (uint32_t)p.N * 2u);
-          bcol = __builtin_amdgcn_raw_buffer_load_b64(rbias, (int)(t < 64 ? (uint32_t)(cur.n0 + 4 * t) * 2u : PF_OOB), 0, 0);
-        } else {
-          const __amdgpu_buffer_rsrc_t rbias = pf_rsrc(bias, bias ? (uint32_t)p.M * 2u : 0u);
-          const uint32_t mb = (uint32_t)(cur.m0 + wm * 128 + ml) * 2u;
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            bmp[i] = __builtin_amdgcn_raw_buffer_load_b16(rbias, (int)(mb + (uint32_t)(i * 32) * 2u), 0, 0);
-        }
+        fetch_bias(nxt, bcol);               // the next tile's (a repeat of this one's after the last)
       }
       issue(0, tt);
       multiply(0);
@@ -551,10 +587,7 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
     // (thread index rebuilt from the wave number in a scalar register and the lane count, so that
     // it is not carried in a vector register through the k-loop)
     const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-    if (COLB && wave_s == 0) {
-      uint2 bv; bv.x = bcol.x; bv.y = bcol.y;
-      sbias[lane_e] = bv;
-    }
+    park_bias(bcol);
     __syncthreads();
 
     // epilogue (see gemm_big_kernel): lane l holds row l % 32 and columns 8*(v/4) + 4*(l/32) + v%4
@@ -571,39 +604,21 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
       const int n = cur.n0 + (tq % (256 / EPV)) * EPV;
       const uint32_t col_byte = n + EPV <= p.N
           ? (uint32_t)((to_partial ? (int64_t)n : col_offset(n, cs, p.c_seg_stride)) * ES) : PF_OOB;
-      uint2 cbp[2][4];                                   // this lane's 32 column biases, packed
-      if (COLB) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) cbp[j][q] = sbias[(wn * 64 + j * 32 + 8 * q + nq) >> 2];
-      }
 #pragma unroll
       for (int pass = 0; pass < 256 / RP; ++pass) {
-        if (wm == pass * RP / 128) {
+        if (RP >= 128 ? (wm * 128) / RP == pass : wm == pass * RP / 128) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const int row = i * 32;
-            if (row / RP != (pass * RP % 128) / RP) continue;
-            const int rl = row % RP + ml;
-            const float bm = COLB ? 0.f : __uint_as_float((uint32_t)bmp[i] << 16);
+            if (RP < 128 && (i * 32) / RP != (pass * RP % 128) / RP) continue;   // this 32-row block's pass
+            const int rl = (wm * 128 + i * 32) % RP + ml;
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
                 const int nl = wn * 64 + j * 32 + 8 * q + nq;
-                float cbv[4] = {bm, bm, bm, bm};
-                if (COLB) {
-                  uint2 cb = cbp[j][q];
-                  asm volatile("" : "+v"(cb.x), "+v"(cb.y));   // unpack at each use: 16 registers, not 32
-                  cbv[0] = __uint_as_float(cb.x << 16);
-                  cbv[1] = __uint_as_float(cb.x & 0xffff0000u);
-                  cbv[2] = __uint_as_float(cb.y << 16);
-                  cbv[3] = __uint_as_float(cb.y & 0xffff0000u);
-                }
                 float x[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) x[e] = big_act<ACT>(acc[i][j][4 * q + e] + cbv[e], neg_slope);
+                for (int e = 0; e < 4; ++e) x[e] = big_act<ACT>(acc[i][j][4 * q + e], neg_slope);
                 unsigned char* dst = smem + rl * PITCH + nl * ES;
                 if (ES == 2) {
                   uint2 o;
