@@ -452,6 +452,68 @@ __global__ __launch_bounds__(1024) void pointwise_loss_kernel(const T* __restric
   if (threadIdx.x == 0) loss[b] = s * invR;
 }
 
+// Long contiguous rows (a regression target per token and feature): one workgroup per model cannot
+// pull a row through one compute unit fast enough, so the gradient is a full-width elementwise
+// launch over all B*R elements in 16-byte pieces and the loss of model b a second, one-workgroup
+// sum over its row (fixed order: per-thread strided partial sums, then the workgroup sum), which
+// re-reads what the first launch has just pulled through the cache.
+template <int KIND>
+__device__ __forceinline__ void pointwise_term(float z, float t, float& loss, float& g) {
+  if (KIND == 0) {
+    loss = fmaxf(z, 0.f) - z * t + log1pf(expf(-fabsf(z)));
+    g = 1.f / (1.f + expf(-z)) - t;
+  } else {
+    const float d = z - t;
+    loss = d * d;
+    g = 2.f * d;
+  }
+}
+
+template <typename T, int KIND>
+__global__ __launch_bounds__(256) void pointwise_grad_vec_kernel(const uint4* __restrict__ pred, const uint4* __restrict__ target,
+                                                                uint4* __restrict__ dpred, int64_t nvec, float invR) {
+  constexpr int N = V16<T>::N;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    float z[N], t[N];
+    V16<T>::unpack(pred[i], z);
+    V16<T>::unpack(target[i], t);
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      float l, g;
+      pointwise_term<KIND>(z[e], t[e], l, g);
+      z[e] = g * invR;
+    }
+    dpred[i] = V16<T>::pack(z);
+  }
+}
+
+template <typename T, int KIND>
+__global__ __launch_bounds__(1024) void pointwise_loss_vec_kernel(const uint4* __restrict__ pred, const uint4* __restrict__ target,
+                                                                 float* __restrict__ loss, int64_t vec_per_row, float invR) {
+  __shared__ float sh[16];
+  constexpr int N = V16<T>::N;
+  const uint4* pr = pred + (int64_t)blockIdx.x * vec_per_row;
+  const uint4* tg = target + (int64_t)blockIdx.x * vec_per_row;
+  float acc = 0.f;
+#pragma unroll 4
+  for (int64_t i = threadIdx.x; i < vec_per_row; i += 1024) {
+    float z[N], t[N];
+    V16<T>::unpack(pr[i], z);
+    V16<T>::unpack(tg[i], t);
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      float l, g;
+      pointwise_term<KIND>(z[e], t[e], l, g);
+      acc += l;
+    }
+  }
+  const float s = block_sum_1024(acc, sh);
+  if (threadIdx.x == 0) loss[blockIdx.x] = s * invR;
+}
+
+// rows at least this long take the two-launch form when they are contiguous and 16-byte aligned
+constexpr int64_t POINTWISE_WIDE_MIN_R = 1 << 16;
+
 unsigned stream_blocks(int64_t n) {
   int64_t b = (n + 255) / 256;
   const int64_t cap = 256 * 32;
@@ -484,6 +546,26 @@ static void launch_act_bwd_vec(const void* Z, const void* dY, void* dX, int64_t 
     case HFTA_ACT_GELU: hipLaunchKernelGGL((act_bwd_vec_kernel<T, HFTA_ACT_GELU, FROM_OUT>), g, b, 0, st, z, dy, dx, nvec, slope); break;
     default: hipLaunchKernelGGL((act_bwd_vec_kernel<T, HFTA_ACT_NONE, FROM_OUT>), g, b, 0, st, z, dy, dx, nvec, slope); break;
   }
+}
+
+// Wide form of the pointwise losses; false when the layout does not allow it.
+template <int KIND>
+static bool launch_pointwise_wide(int B, int64_t R, int dtype, const void* pred, const void* target, float* loss,
+                                  void* dpred, int64_t sb, int64_t sr, hipStream_t st) {
+  const int per = dtype == HFTA_BF16 ? 8 : 4;
+  if (sr != 1 || sb != R || R < POINTWISE_WIDE_MIN_R || R % per != 0 || !al16(pred) || !al16(target) || !al16(dpred))
+    return false;
+  const int64_t vpr = R / per, nvec = vpr * B;
+  const float invR = 1.f / (float)R;
+  const uint4* p4 = (const uint4*)pred; const uint4* t4 = (const uint4*)target; uint4* d4 = (uint4*)dpred;
+  if (dtype == HFTA_BF16) {
+    hipLaunchKernelGGL((pointwise_grad_vec_kernel<bf16_raw, KIND>), dim3(stream_blocks(nvec)), dim3(256), 0, st, p4, t4, d4, nvec, invR);
+    hipLaunchKernelGGL((pointwise_loss_vec_kernel<bf16_raw, KIND>), dim3((unsigned)B), dim3(1024), 0, st, p4, t4, loss, vpr, invR);
+  } else {
+    hipLaunchKernelGGL((pointwise_grad_vec_kernel<float, KIND>), dim3(stream_blocks(nvec)), dim3(256), 0, st, p4, t4, d4, nvec, invR);
+    hipLaunchKernelGGL((pointwise_loss_vec_kernel<float, KIND>), dim3((unsigned)B), dim3(1024), 0, st, p4, t4, loss, vpr, invR);
+  }
+  return true;
 }
 
 }  // namespace
@@ -692,6 +774,8 @@ int hfta_bce_logits_strided(int B, int64_t R, int dtype, const void* logits, con
                             void* dlogits, int64_t stride_b, int64_t stride_r, void* stream) {
   if (B <= 0 || R <= 0 || !valid_dtype(dtype) || !logits || !targets || !loss || !dlogits) return HFTA_EINVAL;
   if (stride_b <= 0 || stride_r <= 0) return HFTA_EINVAL;
+  if (launch_pointwise_wide<0>(B, R, dtype, logits, targets, loss, dlogits, stride_b, stride_r, as_stream(stream)))
+    return launch_status();
   if (dtype == HFTA_BF16)
     hipLaunchKernelGGL((pointwise_loss_kernel<bf16_raw, 0>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
                        (const bf16_raw*)logits, (const bf16_raw*)targets, loss, (bf16_raw*)dlogits, R, stride_b, stride_r);
@@ -708,6 +792,7 @@ int hfta_bce_logits(int B, int64_t R, int dtype, const void* logits, const void*
 
 int hfta_mse(int B, int64_t R, int dtype, const void* pred, const void* target, float* loss, void* dpred, void* stream) {
   if (B <= 0 || R <= 0 || !valid_dtype(dtype) || !pred || !target || !loss || !dpred) return HFTA_EINVAL;
+  if (launch_pointwise_wide<1>(B, R, dtype, pred, target, loss, dpred, R, 1, as_stream(stream))) return launch_status();
   if (dtype == HFTA_BF16)
     hipLaunchKernelGGL((pointwise_loss_kernel<bf16_raw, 1>), dim3((unsigned)B), dim3(1024), 0, as_stream(stream),
                        (const bf16_raw*)pred, (const bf16_raw*)target, loss, (bf16_raw*)dpred, R, R, (int64_t)1);

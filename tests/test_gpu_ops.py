@@ -494,6 +494,19 @@ def test_losses(hb, dtype):
     rl, rdp = oa.bce_logits(B, p, tb)
     check(host(loss), rl, 1e-5, "bce loss")
     check(host(dp), rdp, TOL[dtype], "dlogits(bce)")
+    # long contiguous rows: full-width gradient launch + one-workgroup loss sum per model
+    R3 = 65536 + 24
+    p, t = hi.normal(96, (B, R3), dtype), hi.normal(97, (B, R3), dtype)
+    dp = empty((B, R3), dtype)
+    hb.mse(B, R3, DT[dtype], dev(p, dtype), dev(t, dtype), loss, dp)
+    rl, rdp = oa.mse(B, p, t)
+    check(host(loss), rl, 1e-5, "mse loss (long rows)")
+    check(host(dp), rdp, TOL[dtype], "dpred (long rows)")
+    tb = (np.random.default_rng(98).random((B, R3)) > 0.5).astype(np.float32)
+    hb.bce_logits(B, R3, DT[dtype], dev(p, dtype), dev(tb, dtype), loss, dp)
+    rl, rdp = oa.bce_logits(B, p, tb)
+    check(host(loss), rl, 1e-5, "bce loss (long rows)")
+    check(host(dp), rdp, TOL[dtype], "dlogits(bce, long rows)")
 
 
 # ------------------------------------------------------------------ grouped Conv2d / ConvTranspose2d
