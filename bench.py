@@ -95,20 +95,20 @@ def kernel_label(name, a):
         if dt == 1 and Ci % 8 == 0 and L % 4 == 0 and ((Ci <= 128 and Co >= 64) or (Ci <= 256 and Co >= 512)):
             return "conv1x1_stream_kernel"
         if dt == 1 and big_gemm(B * Nb, Co, L, Ci):
-            return "gemm_big_kernel(fwd)"
+            return big_name(B * Nb, Co, L) + "(fwd)"
         return "gemm_pf_kernel(fwd)" if dt == 1 else "gemm_kernel(fwd)"
     if name == "linear_fwd_ws" and a[1] <= 64:
         return ("gemm_pf_kernel" if a[4] == 1 else "gemm_kernel") + "(fwd, split)+splitk_bias_act_kernel"
     if name in ("linear_fwd", "linear_fwd_ws"):
         if a[4] == 1 and big_gemm(a[0], a[1], a[3], a[2]):
-            return "gemm_big_kernel(fwd)"
+            return big_name(a[0], a[1], a[3]) + "(fwd)"
         return "gemm_pf_kernel(fwd)" if a[4] == 1 else "gemm_kernel(fwd)"
     if name == "linear_bwd":           # the MLP array asks for dX, dW and dbias in separate calls
         B, M, Fx, Fy, dt = a[:5]
         if a[8] is not None and a[9] is not None:      # one call for everything (the Transformer array)
             return "linear_bwd: gemm(dX) + gemm(dW) + splitk_reduce_kernel + colsum_kernel"
         if a[8] is not None:
-            return ("gemm_big_kernel" if dt == 1 and big_gemm(B, M, Fx, Fy) else "gemm_pf_kernel") + "(dX)"
+            return (big_name(B, M, Fx) if dt == 1 and big_gemm(B, M, Fx, Fy) else "gemm_pf_kernel") + "(dX)"
         if a[9] is not None:
             return ("gemm_big_kernel" if dt == 1 and big_gemm_split(B, Fx, Fy, M) else "gemm_pf_kernel") + "(dW)"
         return "colsum_kernel"
@@ -141,7 +141,7 @@ def kernel_label(name, a):
             if (dt == 1 and Co % 8 == 0 and L % 4 == 0 and a[15] is not None
                     and ((Co <= 128 and Ci >= 64) or (Co <= 256 and Ci >= 512))):
                 return "conv1x1_stream_kernel(dX)"
-            return ("gemm_big_kernel" if dt == 1 and big_gemm(B * Nb, Ci, L, Co) else k) + "(dX)"
+            return (big_name(B * Nb, Ci, L) if dt == 1 and big_gemm(B * Nb, Ci, L, Co) else k) + "(dX)"
         if dt == 1 and big_gemm_split(B, Co, Ci, L, Nb):
             k = "gemm_big_kernel"
         return k + "(dW)+splitk_reduce_kernel"
@@ -158,6 +158,14 @@ def kernel_label(name, a):
 def big_gemm(G, M, N, K):
     """The 256x256-tile kernel's dispatch rule (compute-bound shapes)."""
     return M >= 192 and N >= 192 and K >= 256 and ((M + 255) // 256) * ((N + 255) // 256) * G >= 192
+
+
+def big_name(G, M, N):
+    """Persistent form of the 256x256-tile kernel: more tiles than compute units, whole 16-byte
+    pieces along the output rows (unsplit launches; the operands' own alignment follows from the
+    same sizes in the workloads here)."""
+    tiles = ((M + 255) // 256) * ((N + 255) // 256) * G
+    return "gemm_bigp_kernel" if tiles > 256 and N % 8 == 0 else "gemm_big_kernel"
 
 
 def big_gemm_split(G, M, N, K, S=1):

@@ -377,42 +377,49 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_big_kernel(GemmArgs p) {
 // the wait for the prefetched loads does not have to cover the stores behind them.  The epilogue
 // is vector-ALU bound (two waves per SIMD, nothing to overlap it), so no activation (BIG_NONE) is a
 // compile-time case of its own rather than a select with slope 1.
-// Host side guarantees: 16-byte loadable operands, 16-byte aligned output rows, N a multiple of the
-// store piece, output slice below 2 GiB.
+// Host side guarantees: operands loadable in whole pieces of the width the instantiation uses,
+// output rows aligned to the store piece (16 or 8 bytes), N a multiple of it, output slice below
+// 2 GiB.
 // rows staged per epilogue pass: the whole tile for 2-byte outputs (133 KB of the 144 KB the k-loop's
 // tiles leave free: every wave converts at the same time), a quarter of it for 4-byte outputs
 constexpr int BIGP_RP(int es) { return es == 2 ? 256 : 64; }
 static_assert(256 * BIG_EPI_PITCH <= BIG_SMEM && 64 * BIG_EPI_PITCH4 <= BIG_SMEM, "staging must fit the tile buffers");
 
-template <typename OutT>
+template <typename OutT, int VB>
 __device__ __forceinline__ void bigp_store_rows(const unsigned char* smem, __amdgpu_buffer_rsrc_t rc, uint32_t c_ldb,
                                                 int M, int mbase, uint32_t col_byte, int t) {
   constexpr int ES = sizeof(OutT);
   constexpr int RP = BIGP_RP(ES);
   constexpr int PITCH = ES == 2 ? BIG_EPI_PITCH : BIG_EPI_PITCH4;
-  constexpr int EPV = 16 / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
+  constexpr int EPV = VB / ES, PPR = 256 / EPV, RPI = BIG_THREADS / PPR;
   const int r0 = t / PPR, c = t % PPR;
   constexpr int NIT = RP / RPI;                          // pieces per thread, read NB at a time
   constexpr int NB = ES == 2 ? 4 : 2;
+  typedef typename std::conditional<VB == 16, uint4, uint2>::type V;
 #pragma unroll
   for (int h = 0; h < NIT; h += NB) {
-    uint4 v[NB];
+    V v[NB];
 #pragma unroll
     for (int it = 0; it < NB; ++it)
-      v[it] = *reinterpret_cast<const uint4*>(smem + (r0 + (h + it) * RPI) * PITCH + c * 16);
+      v[it] = *reinterpret_cast<const V*>(smem + (r0 + (h + it) * RPI) * PITCH + c * VB);
 #pragma unroll
     for (int it = 0; it < NB; ++it) {
       const int m = mbase + r0 + (h + it) * RPI;
       const uint32_t off = (m < M && col_byte != PF_OOB) ? (uint32_t)m * c_ldb + col_byte : PF_OOB;
-      pf_u32x4 w; w.x = v[it].x; w.y = v[it].y; w.z = v[it].z; w.w = v[it].w;
-      __builtin_amdgcn_raw_buffer_store_b128(w, rc, (int)off, 0, 0);
+      if constexpr (VB == 16) {
+        pf_u32x4 w; w.x = v[it].x; w.y = v[it].y; w.z = v[it].z; w.w = v[it].w;
+        __builtin_amdgcn_raw_buffer_store_b128(w, rc, (int)off, 0, 0);
+      } else {
+        pf_u32x2 w; w.x = v[it].x; w.y = v[it].y;
+        __builtin_amdgcn_raw_buffer_store_b64(w, rc, (int)off, 0, 0);
+      }
     }
   }
 }
 
 struct BigCoord { int m0, n0, g0, g1, split, g, t_begin, t_end; };
 
-template <bool A_KC, bool B_KC, typename OutT, bool COLB, int ACT>
+template <bool A_KC, bool B_KC, typename OutT, bool COLB, int ACT, bool V16, bool N16>
 __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int vgx, int vtotal) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[BIG_SMEM];
   __shared__ uint2 sbias[64];                            // this tile's 256 column biases (an object of its own:
@@ -447,10 +454,10 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
   };
 
   // loader state: the tile whose k-tiles are being fetched
-  BigOp<A_KC, true, true> oa;
-  BigOp<B_KC, true, true> ob;
-  typename BigOp<A_KC, true, true>::Regs ra[BIG_PF];
-  typename BigOp<B_KC, true, true>::Regs rb[BIG_PF];
+  BigOp<A_KC, V16, N16> oa;
+  BigOp<B_KC, V16, N16> ob;
+  typename BigOp<A_KC, V16, N16>::Regs ra[BIG_PF];
+  typename BigOp<B_KC, V16, N16>::Regs rb[BIG_PF];
   const bf16_raw* Ab;
   const bf16_raw* Bb;
   int l_end;
@@ -601,8 +608,10 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
       // segment division's reciprocal is carried in registers through the k-loop
       int tq = wave_s * 64 + lane_e, cs = p.c_seg;
       asm volatile("" : "+v"(tq), "+s"(cs));
-      const int n = cur.n0 + (tq % (256 / EPV)) * EPV;
-      const uint32_t col_byte = n + EPV <= p.N
+      const int vb = to_partial ? p.p_vec : p.c_vec;     // 16- or 8-byte store pieces
+      const int epv = vb / ES;
+      const int n = cur.n0 + (tq % (256 / epv)) * epv;
+      const uint32_t col_byte = n + epv <= p.N
           ? (uint32_t)((to_partial ? (int64_t)n : col_offset(n, cs, p.c_seg_stride)) * ES) : PF_OOB;
 #pragma unroll
       for (int pass = 0; pass < 256 / RP; ++pass) {
@@ -632,7 +641,8 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
           }
         }
         __syncthreads();
-        bigp_store_rows<OutT>(smem, rc, c_ldb, p.M, cur.m0 + pass * RP, col_byte, t);
+        if (vb == 16) bigp_store_rows<OutT, 16>(smem, rc, c_ldb, p.M, cur.m0 + pass * RP, col_byte, t);
+        else bigp_store_rows<OutT, 8>(smem, rc, c_ldb, p.M, cur.m0 + pass * RP, col_byte, t);
         __syncthreads();
       }
     }

@@ -26,24 +26,38 @@ static int persistent_blocks() {
   return n;
 }
 
-template <bool A_KC, bool B_KC, typename OutT, bool COLB>
-static void launch_bigp(const GemmArgs& a, bool ident, dim3 grid, int blocks, hipStream_t st) {
+template <bool A_KC, bool B_KC, typename OutT, bool COLB, bool V16, bool N16>
+static void launch_bigp2(const GemmArgs& a, bool ident, dim3 grid, int blocks, hipStream_t st) {
   if (ident)
-    hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_NONE>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0, st, a,
+    hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_NONE, V16, N16>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0, st, a,
                        (int)grid.x, (int)(grid.x * grid.z));
   else
-    hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_SEL>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0, st, a,
+    hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_SEL, V16, N16>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0, st, a,
                        (int)grid.x, (int)(grid.x * grid.z));
 }
 
-static bool persistent_ok(const GemmDesc& d, const GemmArgs& a, bool n16, bool sel, dim3 grid, int blocks) {
+// One load-width flag matters per operand pair: v16 for two k-contiguous operands, n16 otherwise
+// (a k-contiguous operand next to an m/n-contiguous one always loads 16-byte pieces here).
+template <bool A_KC, bool B_KC, typename OutT, bool COLB>
+static void launch_bigp(const GemmArgs& a, bool ident, bool v16, bool n16, dim3 grid, int blocks, hipStream_t st) {
+  if constexpr (A_KC && B_KC) {
+    if (v16) launch_bigp2<A_KC, B_KC, OutT, COLB, true, false>(a, ident, grid, blocks, st);
+    else launch_bigp2<A_KC, B_KC, OutT, COLB, false, false>(a, ident, grid, blocks, st);
+  } else {
+    if (n16) launch_bigp2<A_KC, B_KC, OutT, COLB, true, true>(a, ident, grid, blocks, st);
+    else launch_bigp2<A_KC, B_KC, OutT, COLB, true, false>(a, ident, grid, blocks, st);
+  }
+}
+
+static bool persistent_ok(const GemmDesc& d, const GemmArgs& a, bool v16, bool sel, dim3 grid, int blocks) {
   if (blocks < 8 || (int64_t)grid.x * grid.z <= blocks || !sel) return false;
-  if (!n16 && !(d.a_kc && d.b_kc)) return false;
+  if (!v16 && !(d.a_kc && d.b_kc)) return false;       // 8-byte k-contiguous loads: both operands only
   const bool partial = a.splits > 1;
   const int oes = (d.out_f32 || partial) ? 4 : 2;
-  if (d.N % (16 / oes) != 0) return false;
-  if (partial) return a.p_vec == 16 && (int64_t)d.M * d.N * 4 < (int64_t)1 << 31;
-  return a.c_vec == 16 && a.c_extent != 0;
+  const int vb = partial ? a.p_vec : a.c_vec;
+  if ((vb != 16 && vb != 8) || d.N % (vb / oes) != 0) return false;
+  if (partial) return (int64_t)d.M * d.N * 4 < (int64_t)1 << 31;
+  return a.c_extent != 0;
 }
 
 // `a` must carry tile counts for 256x256 tiles and 64-element k-tiles and operand extents.
@@ -58,28 +72,28 @@ int gemm_big_launch(const GemmDesc& d, const GemmArgs& a0, bool v16, bool n16, d
   a.slope = d.act == HFTA_ACT_NONE ? 1.f : d.act == HFTA_ACT_RELU ? 0.f : d.slope;
   if (colb && (reinterpret_cast<uintptr_t>(d.bias) % 8 != 0 || d.bias_g0 % 4 != 0 || d.bias_g1 % 4 != 0 || d.N % 4 != 0))
     return HFTA_EUNSUPPORTED;
+  const int blocks = persistent_blocks();
+  if (persistent_ok(d, a, v16, sel, grid, blocks)) {
+    const bool f32 = d.out_f32 || a.splits > 1;
+    const bool ident = d.act == HFTA_ACT_NONE;
+    if (f32 && !colb) {
+      if (d.a_kc && !d.b_kc) { launch_bigp<true, false, float, false>(a, ident, v16, n16, grid, blocks, st); return launch_status(); }
+      if (d.a_kc && d.b_kc) { launch_bigp<true, true, float, false>(a, ident, v16, n16, grid, blocks, st); return launch_status(); }
+      if (!d.a_kc && !d.b_kc) { launch_bigp<false, false, float, false>(a, ident, v16, n16, grid, blocks, st); return launch_status(); }
+    } else if (!f32) {
+      if (d.a_kc && !d.b_kc) {
+        if (colb) launch_bigp<true, false, bf16_raw, true>(a, ident, v16, n16, grid, blocks, st);
+        else launch_bigp<true, false, bf16_raw, false>(a, ident, v16, n16, grid, blocks, st);
+        return launch_status();
+      }
+      if (!colb && d.a_kc && d.b_kc) { launch_bigp<true, true, bf16_raw, false>(a, ident, v16, n16, grid, blocks, st); return launch_status(); }
+      if (!colb && !d.a_kc && !d.b_kc) { launch_bigp<false, false, bf16_raw, false>(a, ident, v16, n16, grid, blocks, st); return launch_status(); }
+    }
+  }
   if (!v16) {
     if (!(d.out_f32 && d.a_kc && d.b_kc) || colb || !sel) return HFTA_EUNSUPPORTED;
     hipLaunchKernelGGL((gemm_big_kernel<true, true, float, false, false, BIG_SEL>), grid, dim3(BIG_THREADS), 0, st, a);
     return launch_status();
-  }
-  const int blocks = persistent_blocks();
-  if (persistent_ok(d, a, n16, sel, grid, blocks)) {
-    const bool f32 = d.out_f32 || a.splits > 1;
-    const bool ident = d.act == HFTA_ACT_NONE;
-    if (f32 && !colb) {
-      if (d.a_kc && !d.b_kc) { launch_bigp<true, false, float, false>(a, ident, grid, blocks, st); return launch_status(); }
-      if (d.a_kc && d.b_kc) { launch_bigp<true, true, float, false>(a, ident, grid, blocks, st); return launch_status(); }
-      if (!d.a_kc && !d.b_kc) { launch_bigp<false, false, float, false>(a, ident, grid, blocks, st); return launch_status(); }
-    } else if (!f32) {
-      if (d.a_kc && !d.b_kc) {
-        if (colb) launch_bigp<true, false, bf16_raw, true>(a, ident, grid, blocks, st);
-        else launch_bigp<true, false, bf16_raw, false>(a, ident, grid, blocks, st);
-        return launch_status();
-      }
-      if (!colb && d.a_kc && d.b_kc) { launch_bigp<true, true, bf16_raw, false>(a, ident, grid, blocks, st); return launch_status(); }
-      if (!colb && !d.a_kc && !d.b_kc) { launch_bigp<false, false, bf16_raw, false>(a, ident, grid, blocks, st); return launch_status(); }
-    }
   }
   if (d.out_f32) {
     if (colb || !sel) return HFTA_EUNSUPPORTED;

@@ -117,7 +117,9 @@ def test_linear_fwd_with_workspace(hb, dtype, B, M, Fx, Fy, act):
                                           (2, 2, 128, 64, 260), (2, 2, 256, 520, 260), (2, 2, 520, 256, 132),
                                           (1, 2, 200, 512, 132),
                                           # more 256x256 tiles than compute units: the persistent GEMM form
-                                          (3, 32, 264, 520, 520)])
+                                          (3, 32, 264, 520, 520),
+                                          # ... with rows of points only 8-byte aligned (8-byte loads and stores)
+                                          (3, 32, 264, 520, 524)])
 def test_conv1x1_fwd_bwd(hb, dtype, B, Nb, Ci, Co, L):
     print(f"conv1x1 {dtype} B={B} Nb={Nb} Ci={Ci} Co={Co} L={L}", flush=True)
     x = hi.normal(11, (Nb, B * Ci, L), dtype)
