@@ -110,7 +110,8 @@ def kernel_label(name, a):
         if a[8] is not None:
             return (big_name(B, M, Fx) if dt == 1 and big_gemm(B, M, Fx, Fy) else "gemm_pf_kernel") + "(dX)"
         if a[9] is not None:
-            return ("gemm_big_kernel" if dt == 1 and big_gemm_split(B, Fx, Fy, M) else "gemm_pf_kernel") + "(dW)"
+            sp = big_splits(B, Fx, Fy, M) if dt == 1 else 0
+            return (big_name(B, Fx, Fy, sp) if sp else "gemm_pf_kernel") + "(dW)"
         return "colsum_kernel"
     if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
@@ -142,8 +143,9 @@ def kernel_label(name, a):
                     and ((Co <= 128 and Ci >= 64) or (Co <= 256 and Ci >= 512))):
                 return "conv1x1_stream_kernel(dX)"
             return (big_name(B * Nb, Ci, L) if dt == 1 and big_gemm(B * Nb, Ci, L, Co) else k) + "(dX)"
-        if dt == 1 and big_gemm_split(B, Co, Ci, L, Nb):
-            k = "gemm_big_kernel"
+        sp = big_splits(B, Co, Ci, L, Nb) if dt == 1 else 0
+        if sp:
+            k = big_name(B, Co, Ci, sp)
         return k + "(dW)+splitk_reduce_kernel"
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
@@ -160,21 +162,38 @@ def big_gemm(G, M, N, K):
     return M >= 192 and N >= 192 and K >= 256 and ((M + 255) // 256) * ((N + 255) // 256) * G >= 192
 
 
-def big_name(G, M, N):
-    """Persistent form of the 256x256-tile kernel: more tiles than compute units, whole 16-byte
-    pieces along the output rows (unsplit launches; the operands' own alignment follows from the
-    same sizes in the workloads here)."""
-    tiles = ((M + 255) // 256) * ((N + 255) // 256) * G
-    return "gemm_bigp_kernel" if tiles > 256 and N % 8 == 0 else "gemm_big_kernel"
+def big_name(G, M, N, splits=1):
+    """Persistent form of the 256x256-tile kernel: more workgroups than compute units and output
+    rows (fp32 partial rows when split) that take whole 8- or 16-byte pieces."""
+    tiles = ((M + 255) // 256) * ((N + 255) // 256) * G * splits
+    return "gemm_bigp_kernel" if tiles > 256 and N % 4 == 0 else "gemm_big_kernel"
+
+
+def big_splits(G, M, N, K, S=1):
+    """Split count the library's cost model picks for a weight gradient on the 256x256-tile kernel
+    (rounds of 256 workgroups, a fixed prologue / epilogue in k-tile units, the partial buffer's
+    traffic), or 0 when the shape does not take that kernel."""
+    if M < 192 or N < 192 or K < 256:
+        return 0
+    t256, tt = ((M + 255) // 256) * ((N + 255) // 256) * G, S * ((K + 63) // 64)
+    if tt < 32:
+        return 0
+    best, best_cost = 0, 0.0
+    for s in range(1, 33):
+        if tt // s < 16:
+            break
+        if t256 * s < 192:
+            continue
+        rounds = (t256 * s + 255) // 256
+        cost = rounds * (tt / s + 4.0) + (0.2 * t256 / 256.0 * s if s > 1 else 0.0)
+        if best == 0 or cost < best_cost:
+            best, best_cost = s, cost
+    return best
 
 
 def big_gemm_split(G, M, N, K, S=1):
-    """Weight-gradient shapes that run split over k on the 256x256-tile kernel: some split count
-    keeps at least 16 k-tiles per workgroup and gives at least 192 workgroups."""
-    if M < 192 or N < 192 or K < 256:
-        return False
-    t256, tt = ((M + 255) // 256) * ((N + 255) // 256) * G, S * ((K + 63) // 64)
-    return tt >= 32 and any(t256 * s >= 192 for s in range(1, 33) if tt // s >= 16)
+    """Weight-gradient shapes that run (possibly split over k) on the 256x256-tile kernel."""
+    return big_splits(G, M, N, K, S) > 0
 
 
 def algorithmic_flops(name, a):
