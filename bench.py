@@ -335,7 +335,7 @@ def ops_report(torch, binding):
     bf = torch.bfloat16
     MFMA_PEAK = 2500.0          # TFLOP/s, dense bf16
 
-    def timeit(fn, n=20, warm=5):
+    def timeit(fn, n=100, warm=30):
         for _ in range(warm):
             fn()
         s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
