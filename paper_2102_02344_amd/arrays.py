@@ -548,13 +548,17 @@ class FusedMlp(ParamArena):
               dw=self.g(k + ".w2"), db=self.g(k + ".b2"))
             hb.act_bwd(B * R * H, dt, self.u[i], self.dH[0], self.dH[1], hb.ACT_GELU)
             P("act_bwd", layer=k, x=self.u[i], dy=self.dH[0], dx=self.dH[1], act=hb.ACT_GELU)
-            hb.linear_bwd(B, R, E, H, dt, None, self.w(k + ".w1"), self.dH[1], dxl, None, None, None)
+            # nothing consumes the gradient of the array's input: the first block computes neither the
+            # data gradient of its first Linear nor the sum that would carry it further
+            if i > 0:
+                hb.linear_bwd(B, R, E, H, dt, None, self.w(k + ".w1"), self.dH[1], dxl, None, None, None)
             hb.linear_bwd(B, R, E, H, dt, self.x[i], None, self.dH[1], None, self.g(k + ".w1"), None, self.ws)
             hb.linear_bwd(B, R, E, H, dt, None, None, self.dH[1], None, None, self.g(k + ".b1"), None)
-            P("linear_bwd", layer=k + ".1", x=self.x[i], w=self.w(k + ".w1"), dy=self.dH[1], dx=dxl,
+            P("linear_bwd", layer=k + ".1", x=self.x[i], w=self.w(k + ".w1"), dy=self.dH[1], dx=dxl if i > 0 else None,
               dw=self.g(k + ".w1"), db=self.g(k + ".b1"))
-            hb.add(B * R * E, dt, ds, dxl, d)          # d (this block's incoming gradient) is dead: reuse it
-            P("add", a=ds, b=dxl, y=d)
+            if i > 0:
+                hb.add(B * R * E, dt, ds, dxl, d)      # d (this block's incoming gradient) is dead: reuse it
+                P("add", a=ds, b=dxl, y=d)
         return self.loss
 
 

@@ -60,7 +60,8 @@ def probe_for(spec, seen):
             Fx, Fy = kw["x"].shape[2], kw["dy"].shape[2]
             dx, dw, db = oa.linear_bwd(B, H64(kw["x"]), H64(kw["w"]).reshape(B, Fx, Fy), H64(kw["dy"]))
             ftol = 1e-5 if spec.dtype == "f32" else 2e-4          # fp32 outputs of bf16 operands
-            check(H64(kw["dx"]), dx, tol, f"{lay} linear dx")
+            if kw["dx"] is not None:          # the first block's input gradient is not computed
+                check(H64(kw["dx"]), dx, tol, f"{lay} linear dx")
             check(H64(kw["dw"]).reshape(B, Fx, Fy), dw, ftol, f"{lay} linear dw")
             check(H64(kw["db"]).reshape(B, Fy), db, ftol, f"{lay} linear db")
         elif op == "act_bwd":
@@ -79,7 +80,7 @@ def test_every_call_in_place(dtype):
     seen = []
     arr.forward_backward(probe_for(spec, seen))
     assert seen.count("linear_fwd") == 2 * spec.blocks and seen.count("linear_bwd") == 2 * spec.blocks
-    assert seen.count("layernorm_bwd") == spec.blocks and seen.count("add") == 2 * spec.blocks
+    assert seen.count("layernorm_bwd") == spec.blocks and seen.count("add") == 2 * spec.blocks - 1
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
