@@ -35,7 +35,7 @@ class Tracer:
 
     SINGLE_KERNEL = ("conv1x1_fwd", "conv1x1_bwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
                      "adam_step_multi", "linear_fwd", "linear_fwd_ws", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
-                     "act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd",
+                     "act_fwd", "act_bwd", "act_bwd_colsum", "add", "layernorm_fwd", "layernorm_bwd",
                      "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_fwd",
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
                      "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
@@ -113,7 +113,7 @@ def kernel_label(name, a):
             sp = big_splits(B, Fx, Fy, M) if dt == 1 else 0
             return (big_name(B, Fx, Fy, sp) if sp else "gemm_pf_kernel") + "(dW)"
         return "colsum_kernel"
-    if name in ("act_fwd", "act_bwd", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
+    if name in ("act_fwd", "act_bwd", "act_bwd_colsum", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
     if name in ("attention_fwd", "attention_bwd"):
         return name + ": batched head GEMMs + softmax_rows kernel"
@@ -299,6 +299,8 @@ def algorithmic_bytes(name, a):
         return 2 * a[0] * _es(a[1])
     if name in ("act_bwd", "add"):
         return 3 * a[0] * _es(a[1])
+    if name == "act_bwd_colsum":              # z, dy in, dx out (the column sums are 4 bytes per column)
+        return 3 * a[0] * a[1] * a[2] * _es(a[3])
     if name == "layernorm_fwd":
         return 2 * a[0] * a[1] * a[2] * _es(a[3])
     if name == "layernorm_bwd":

@@ -396,6 +396,15 @@ int hfta_act_fwd(int64_t count, int dtype, const void* X, void* Y, int act, floa
  * RELU, LEAKY with slope > 0, TANH); otherwise Z holds the pre-activation input. */
 int hfta_act_bwd(int64_t count, int dtype, const void* Z, const void* dY, void* dX,
                  int act, float slope, int from_output, void* stream);
+/* hfta_act_bwd (Z = pre-activation input) of a fused Linear's output [B][M][F] together with that
+ * Linear's bias gradient (fusion rules table, Linear row: the bias gradient is the sum over the rows
+ * of the output gradient): dX = dY * act'(Z) in the storage dtype and dbias[b][f] = sum over m of
+ * dX[b][m][f] as stored (fp32 [B][F]), in one pass over the tensors.  Equals hfta_act_bwd followed by
+ * hfta_linear_bwd's dbias up to fp32 summation order.  Device pointers, row-major, dX may alias dY.
+ * EUNSUPPORTED unless F is a multiple of the 16-byte piece (8 bf16 / 4 fp32) and Z, dY, dX are
+ * 16-byte aligned (use the two calls then); EINVAL on null pointers or non-positive sizes. */
+int hfta_act_bwd_colsum(int B, int M, int F, int dtype, const void* Z, const void* dY, void* dX,
+                        float* dbias, int act, float slope, void* stream);
 /* Y = A + B element-wise over `count` elements of the storage dtype (the residual connection of
  * the MLP-block workload; fusion rules table, element-wise operators keep their shape with the
  * model dimension folded in).  Y may alias A or B.  Device pointers; EINVAL on null / count <= 0. */

@@ -546,14 +546,19 @@ class FusedMlp(ParamArena):
             hb.linear_bwd(B, R, H, E, dt, None, None, ds, None, None, self.g(k + ".b2"), None)
             P("linear_bwd", layer=k + ".2", x=self.h[i], w=self.w(k + ".w2"), dy=ds, dx=self.dH[0],
               dw=self.g(k + ".w2"), db=self.g(k + ".b2"))
-            hb.act_bwd(B * R * H, dt, self.u[i], self.dH[0], self.dH[1], hb.ACT_GELU)
+            # GELU backward and the first Linear's bias gradient (column sums of its result) in one pass
+            # (whole 16-byte pieces along H; otherwise the two separate calls)
+            if H % (8 if dt == hb.BF16 else 4) == 0:
+                hb.act_bwd_colsum(B, R, H, dt, self.u[i], self.dH[0], self.dH[1], self.g(k + ".b1"), hb.ACT_GELU)
+            else:
+                hb.act_bwd(B * R * H, dt, self.u[i], self.dH[0], self.dH[1], hb.ACT_GELU)
+                hb.linear_bwd(B, R, E, H, dt, None, None, self.dH[1], None, None, self.g(k + ".b1"), None)
             P("act_bwd", layer=k, x=self.u[i], dy=self.dH[0], dx=self.dH[1], act=hb.ACT_GELU)
             # nothing consumes the gradient of the array's input: the first block computes neither the
             # data gradient of its first Linear nor the sum that would carry it further
             if i > 0:
                 hb.linear_bwd(B, R, E, H, dt, None, self.w(k + ".w1"), self.dH[1], dxl, None, None, None)
             hb.linear_bwd(B, R, E, H, dt, self.x[i], None, self.dH[1], None, self.g(k + ".w1"), None, self.ws)
-            hb.linear_bwd(B, R, E, H, dt, None, None, self.dH[1], None, None, self.g(k + ".b1"), None)
             P("linear_bwd", layer=k + ".1", x=self.x[i], w=self.w(k + ".w1"), dy=self.dH[1], dx=dxl if i > 0 else None,
               dw=self.g(k + ".w1"), db=self.g(k + ".b1"))
             if i > 0:

@@ -86,6 +86,7 @@ _SIGS = {
     "hfta_adam_step_multi": (_i, [_i, _i, _s4, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _i, _i, _p]),
     "hfta_act_fwd": (_i, [_i64, _i, _p, _p, _i, _f, _p]),
     "hfta_act_bwd": (_i, [_i64, _i, _p, _p, _p, _i, _f, _i, _p]),
+    "hfta_act_bwd_colsum": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _i, _f, _p]),
     "hfta_bias_act_nchw": (_i, [_i64, _i64, _i64, _i, _p, _p, _i, _f, _p]),
     "hfta_dropout": (_i, [_i64, _i, _p, _p, _f, _p, _p]),
     "hfta_add": (_i, [_i64, _i, _p, _p, _p, _p]),
@@ -316,6 +317,11 @@ def act_fwd(count, dtype, X, Y, act, slope=0.0, stream=None):
 def act_bwd(count, dtype, Z, dY, dX, act, slope=0.0, from_output=0, stream=None):
     _check(_lib.hfta_act_bwd(count, dtype, _ptr(Z), _ptr(dY), _ptr(dX), act, slope, from_output, _stream(stream)),
            "hfta_act_bwd")
+
+
+def act_bwd_colsum(B, M, F, dtype, Z, dY, dX, dbias, act, slope=0.0, stream=None):
+    _check(_lib.hfta_act_bwd_colsum(B, M, F, dtype, _ptr(Z), _ptr(dY), _ptr(dX), _ptr(dbias), act, slope, _stream(stream)),
+           "hfta_act_bwd_colsum")
 
 
 def bias_act_nchw(Nb, K, HW, dtype, Y, bias, act=ACT_NONE, slope=0.0, stream=None):

@@ -452,6 +452,53 @@ __global__ __launch_bounds__(1024) void pointwise_loss_kernel(const T* __restric
   if (threadIdx.x == 0) loss[b] = s * invR;
 }
 
+// Activation backward of a fused Linear's output fused with that Linear's bias gradient:
+// dX = dY * act'(Z) over [B][M][F] and dbias[b][f] = sum_m dX[b][m][f] (of the values as stored), one
+// pass.  A workgroup owns 16 pieces of 16 bytes along the features x 64 row lanes of one model; row
+// lanes meet in LDS in a fixed order.
+template <typename T, int ACT>
+__global__ __launch_bounds__(1024) void act_bwd_colsum_kernel(const uint4* __restrict__ z, const uint4* __restrict__ dy,
+                                                             uint4* __restrict__ dx, float* __restrict__ out, int M,
+                                                             int F, float slope) {
+  constexpr int N = V16<T>::N;
+  __shared__ float part[64][16 * N + 1];
+  const int b = blockIdx.y;
+  const int cg = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  const int vpr = F / N;
+  const int v = blockIdx.x * 16 + cg;
+  float acc[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) acc[e] = 0.f;
+  if (v < vpr) {
+    const int64_t base = (int64_t)b * M * vpr + v;
+#pragma unroll 4
+    for (int r = rl; r < M; r += 64) {
+      const int64_t at = base + (int64_t)r * vpr;
+      float zz[N], d[N];
+      V16<T>::unpack(z[at], zz);
+      V16<T>::unpack(dy[at], d);
+#pragma unroll
+      for (int e = 0; e < N; ++e) d[e] *= act_deriv_t<ACT, sizeof(T) == 2>(zz[e], slope);
+      const uint4 o = V16<T>::pack(d);
+      dx[at] = o;
+      V16<T>::unpack(o, d);                 // the column sum is of the stored values
+#pragma unroll
+      for (int e = 0; e < N; ++e) acc[e] += d[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) part[rl][cg * N + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < 16 * N) {
+    const int col = blockIdx.x * 16 * N + threadIdx.x;
+    if (col < F) {
+      float s = 0.f;
+      for (int r = 0; r < 64; ++r) s += part[r][threadIdx.x];
+      out[(int64_t)b * F + col] = s;
+    }
+  }
+}
+
 // Long contiguous rows (a regression target per token and feature): one workgroup per model cannot
 // pull a row through one compute unit fast enough, so the gradient is a full-width elementwise
 // launch over all B*R elements in 16-byte pieces and the loss of model b a second, one-workgroup
@@ -631,6 +678,29 @@ int hfta_act_bwd(int64_t count, int dtype, const void* Z, const void* dY, void* 
       hipLaunchKernelGGL(act_bwd_kernel<float>, dim3(stream_blocks(n)), dim3(256), 0, st, (const float*)Z + done,
                          (const float*)dY + done, (float*)dX + done, n, act, slope, from_output);
   }
+  return launch_status();
+}
+
+int hfta_act_bwd_colsum(int B, int M, int F, int dtype, const void* Z, const void* dY, void* dX, float* dbias, int act,
+                        float slope, void* stream) {
+  if (B <= 0 || M <= 0 || F <= 0 || !valid_dtype(dtype) || !Z || !dY || !dX || !dbias || !valid_act(act)) return HFTA_EINVAL;
+  const int epv = 16 / (int)dtype_size(dtype);
+  if (F % epv != 0 || !al16(Z) || !al16(dY) || !al16(dX) || B > 65535) return HFTA_EUNSUPPORTED;
+  hipStream_t st = as_stream(stream);
+  const dim3 g((unsigned)((F / epv + 15) / 16), (unsigned)B), blk(1024);
+  const uint4* z = (const uint4*)Z; const uint4* dy = (const uint4*)dY; uint4* dx = (uint4*)dX;
+#define HFTA_ABC(T, A) hipLaunchKernelGGL((act_bwd_colsum_kernel<T, A>), g, blk, 0, st, z, dy, dx, dbias, M, F, slope)
+#define HFTA_ABC_T(T) \
+  switch (act) { \
+    case HFTA_ACT_RELU: HFTA_ABC(T, HFTA_ACT_RELU); break; \
+    case HFTA_ACT_LEAKY: HFTA_ABC(T, HFTA_ACT_LEAKY); break; \
+    case HFTA_ACT_TANH: HFTA_ABC(T, HFTA_ACT_TANH); break; \
+    case HFTA_ACT_GELU: HFTA_ABC(T, HFTA_ACT_GELU); break; \
+    default: HFTA_ABC(T, HFTA_ACT_NONE); break; \
+  }
+  if (dtype == HFTA_BF16) { HFTA_ABC_T(bf16_raw) } else { HFTA_ABC_T(float) }
+#undef HFTA_ABC_T
+#undef HFTA_ABC
   return launch_status();
 }
 

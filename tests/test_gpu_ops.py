@@ -475,6 +475,26 @@ def test_layernorm(hb, dtype, B, R, E):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,M,F,act", [(3, 200, 264, "GELU"), (2, 70, 4104, "RELU"), (2, 1, 8, "TANH"), (1, 4100, 128, "LEAKY")])
+def test_act_bwd_with_bias_gradient(hb, dtype, B, M, F, act):
+    """Activation backward fused with the column sums of its result = the two separate operators."""
+    print(f"act_bwd_colsum {dtype} B={B} M={M} F={F} {act}", flush=True)
+    a, oa_act = getattr(hb, "ACT_" + act), getattr(oops, "ACT_" + act)
+    z, dy = hi.normal(61, (B, M, F), dtype), hi.normal(62, (B, M, F), dtype)
+    dx, db = empty((B, M, F), dtype), empty((B, F), torch.float32)
+    hb.act_bwd_colsum(B, M, F, DT[dtype], dev(z, dtype), dev(dy, dtype), dx, db, a, 0.2)
+    rdx = oops.act_bwd(z, dy, oa_act, 0.2)
+    check(host(dx), rdx, TOL[dtype], "dx")
+    # the sums are of the values as stored
+    stored = host(dx).astype(np.float64)
+    check(host(db), stored.sum(axis=1), f32_tol(dtype), "dbias vs stored dx")
+    check(host(db), oops.store(rdx, dtype).sum(axis=1), 5 * TOL[dtype], "dbias vs oracle")
+    if F % 8 == 0 and dtype == "bf16":
+        with pytest.raises(RuntimeError):            # 100 columns: no whole 16-byte pieces
+            hb.act_bwd_colsum(B, M, 100, DT[dtype], dev(z, dtype), dev(dy, dtype), dx, db, a, 0.2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_losses(hb, dtype):
     B, R, K = 3, 77, 16
     z = hi.normal(91, (B, R, K), dtype) * 2
