@@ -32,15 +32,28 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(PoolArgs p) {
   int bi = 0x7fffffff;
   T bbits = T(0);
   if (VEC == 4) {
+    // five pieces per lane in flight (a 2500-point row is two rounds); a piece past the row's end
+    // re-reads the lane's first piece and is skipped
+    constexpr int U = 5;
     const int chunks = p.L / 4;
-    for (int ch = lane; ch < chunks; ch += 64) {
-      T e[4];
-      if (sizeof(T) == 2) *reinterpret_cast<uint2*>(e) = *reinterpret_cast<const uint2*>(x + ch * 4);
-      else *reinterpret_cast<uint4*>(e) = *reinterpret_cast<const uint4*>(x + ch * 4);
+    for (int ch0 = lane; ch0 < chunks; ch0 += 64 * U) {
+      T e[U][4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const float v = Elem<T>::to_f32(e[k]);
-        if (v > best || bi == 0x7fffffff) { best = v; bi = ch * 4 + k; bbits = e[k]; }
+      for (int u = 0; u < U; ++u) {
+        const int ch = ch0 + 64 * u < chunks ? ch0 + 64 * u : ch0;
+        if (sizeof(T) == 2) *reinterpret_cast<uint2*>(e[u]) = *reinterpret_cast<const uint2*>(x + ch * 4);
+        else *reinterpret_cast<uint4*>(e[u]) = *reinterpret_cast<const uint4*>(x + ch * 4);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int ch = ch0 + 64 * u;
+        if (ch < chunks) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const float v = Elem<T>::to_f32(e[u][k]);
+            if (v > best || bi == 0x7fffffff) { best = v; bi = ch * 4 + k; bbits = e[u][k]; }
+          }
+        }
       }
     }
   } else {
