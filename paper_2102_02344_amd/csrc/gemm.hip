@@ -62,7 +62,7 @@ int gemm_pick_splits(const GemmDesc& d) {
   const int64_t tiles = (int64_t)((d.M + GEMM_BM - 1) / GEMM_BM) * ((d.N + GEMM_BN - 1) / GEMM_BN) * d.G0 * d.G1;
   const int tt = total_tiles(d);
   if (tiles >= 512 || tt < 16) return 1;
-  int64_t want = (1024 + tiles - 1) / tiles;
+  int64_t want = (512 + tiles - 1) / tiles;       // two workgroups per compute unit (measured best: 256-1536 swept)
   int64_t cap = tt / 8;
   if (want > cap) want = cap;
   if (want > 256) want = 256;
