@@ -456,7 +456,10 @@ __global__ __launch_bounds__(1024) void pointwise_loss_kernel(const T* __restric
 // dX = dY * act'(Z) over [B][M][F] and dbias[b][f] = sum_m dX[b][m][f] (of the values as stored), one
 // pass.  A workgroup owns 16 pieces of 16 bytes along the features x 64 row lanes of one model; row
 // lanes meet in LDS in a fixed order.
-template <typename T, int ACT>
+// SUM_ONLY: dx is already there (written by the full-width element-wise kernel); only its column sums
+// are formed - the form for few models, where (features / 128) x B workgroups cannot carry the
+// element-wise traffic.
+template <typename T, int ACT, bool SUM_ONLY = false>
 __global__ __launch_bounds__(1024) void act_bwd_colsum_kernel(const uint4* __restrict__ z, const uint4* __restrict__ dy,
                                                              uint4* __restrict__ dx, float* __restrict__ out, int M,
                                                              int F, float slope) {
@@ -475,13 +478,17 @@ __global__ __launch_bounds__(1024) void act_bwd_colsum_kernel(const uint4* __res
     for (int r = rl; r < M; r += 64) {
       const int64_t at = base + (int64_t)r * vpr;
       float zz[N], d[N];
-      V16<T>::unpack(z[at], zz);
-      V16<T>::unpack(dy[at], d);
+      if (SUM_ONLY) {
+        V16<T>::unpack(dx[at], d);
+      } else {
+        V16<T>::unpack(z[at], zz);
+        V16<T>::unpack(dy[at], d);
 #pragma unroll
-      for (int e = 0; e < N; ++e) d[e] *= act_deriv_t<ACT, sizeof(T) == 2>(zz[e], slope);
-      const uint4 o = V16<T>::pack(d);
-      dx[at] = o;
-      V16<T>::unpack(o, d);                 // the column sum is of the stored values
+        for (int e = 0; e < N; ++e) d[e] *= act_deriv_t<ACT, sizeof(T) == 2>(zz[e], slope);
+        const uint4 o = V16<T>::pack(d);
+        dx[at] = o;
+        V16<T>::unpack(o, d);               // the column sum is of the stored values
+      }
 #pragma unroll
       for (int e = 0; e < N; ++e) acc[e] += d[e];
     }
@@ -689,6 +696,17 @@ int hfta_act_bwd_colsum(int B, int M, int F, int dtype, const void* Z, const voi
   hipStream_t st = as_stream(stream);
   const dim3 g((unsigned)((F / epv + 15) / 16), (unsigned)B), blk(1024);
   const uint4* z = (const uint4*)Z; const uint4* dy = (const uint4*)dY; uint4* dx = (uint4*)dX;
+  if ((int64_t)g.x * g.y < 128) {      // too few workgroups for the element-wise traffic: two launches
+    const int64_t nvec = (int64_t)B * M * (F / epv);
+    if (dtype == HFTA_BF16) {
+      launch_act_bwd_vec<bf16_raw, false>(Z, dY, dX, nvec, act, slope, st);
+      hipLaunchKernelGGL((act_bwd_colsum_kernel<bf16_raw, HFTA_ACT_NONE, true>), g, blk, 0, st, z, dy, dx, dbias, M, F, slope);
+    } else {
+      launch_act_bwd_vec<float, false>(Z, dY, dX, nvec, act, slope, st);
+      hipLaunchKernelGGL((act_bwd_colsum_kernel<float, HFTA_ACT_NONE, true>), g, blk, 0, st, z, dy, dx, dbias, M, F, slope);
+    }
+    return launch_status();
+  }
 #define HFTA_ABC(T, A) hipLaunchKernelGGL((act_bwd_colsum_kernel<T, A>), g, blk, 0, st, z, dy, dx, dbias, M, F, slope)
 #define HFTA_ABC_T(T) \
   switch (act) { \

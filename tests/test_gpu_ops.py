@@ -475,7 +475,9 @@ def test_layernorm(hb, dtype, B, R, E):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("B,M,F,act", [(3, 200, 264, "GELU"), (2, 70, 4104, "RELU"), (2, 1, 8, "TANH"), (1, 4100, 128, "LEAKY")])
+@pytest.mark.parametrize("B,M,F,act", [(3, 200, 264, "GELU"), (2, 70, 4104, "RELU"), (2, 1, 8, "TANH"), (1, 4100, 128, "LEAKY"),
+                                       # many models: the one-pass form (at least 128 workgroups)
+                                       (16, 70, 1024, "GELU"), (40, 133, 520, "RELU"), (130, 65, 8, "LEAKY")])
 def test_act_bwd_with_bias_gradient(hb, dtype, B, M, F, act):
     """Activation backward fused with the column sums of its result = the two separate operators."""
     print(f"act_bwd_colsum {dtype} B={B} M={M} F={F} {act}", flush=True)
