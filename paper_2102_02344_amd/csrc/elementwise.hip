@@ -507,10 +507,10 @@ __global__ __launch_bounds__(1024) void act_bwd_colsum_kernel(const uint4* __res
 }
 
 // Long contiguous rows (a regression target per token and feature): one workgroup per model cannot
-// pull a row through one compute unit fast enough, so the gradient is a full-width elementwise
-// launch over all B*R elements in 16-byte pieces and the loss of model b a second, one-workgroup
-// sum over its row (fixed order: per-thread strided partial sums, then the workgroup sum), which
-// re-reads what the first launch has just pulled through the cache.
+// pull a row through one compute unit fast enough, so both the loss and the gradient are full-width
+// launches over all B*R elements in 16-byte pieces: chunk sums of the loss (64 per model, fixed
+// order), their sum, then the element-wise gradient.  The gradient must not alias pred or target
+// here (the chunk sums pass through its buffer before the inputs are read a second time).
 template <int KIND>
 __device__ __forceinline__ void pointwise_term(float z, float t, float& loss, float& g) {
   if (KIND == 0) {
@@ -541,16 +541,24 @@ __global__ __launch_bounds__(256) void pointwise_grad_vec_kernel(const uint4* __
   }
 }
 
+// Loss of model b, first stage: workgroup (s, b) sums chunk s of the row and leaves the partial sum in
+// the first floats of that model's dpred row, which the gradient launch overwrites afterwards (no
+// scratch memory is needed, and the order of the additions is fixed).
+constexpr int POINTWISE_CHUNKS = 64;
 template <typename T, int KIND>
-__global__ __launch_bounds__(1024) void pointwise_loss_vec_kernel(const uint4* __restrict__ pred, const uint4* __restrict__ target,
-                                                                 float* __restrict__ loss, int64_t vec_per_row, float invR) {
+__global__ __launch_bounds__(1024) void pointwise_loss_part_kernel(const uint4* __restrict__ pred, const uint4* __restrict__ target,
+                                                                  uint4* __restrict__ dpred, int64_t vec_per_row) {
   __shared__ float sh[16];
   constexpr int N = V16<T>::N;
-  const uint4* pr = pred + (int64_t)blockIdx.x * vec_per_row;
-  const uint4* tg = target + (int64_t)blockIdx.x * vec_per_row;
+  const int b = blockIdx.y;
+  const int64_t per = (vec_per_row + POINTWISE_CHUNKS - 1) / POINTWISE_CHUNKS;
+  const int64_t lo = (int64_t)blockIdx.x * per;
+  const int64_t hi = lo + per < vec_per_row ? lo + per : vec_per_row;
+  const uint4* pr = pred + (int64_t)b * vec_per_row;
+  const uint4* tg = target + (int64_t)b * vec_per_row;
   float acc = 0.f;
 #pragma unroll 4
-  for (int64_t i = threadIdx.x; i < vec_per_row; i += 1024) {
+  for (int64_t i = lo + threadIdx.x; i < hi; i += 1024) {
     float z[N], t[N];
     V16<T>::unpack(pr[i], z);
     V16<T>::unpack(tg[i], t);
@@ -562,7 +570,17 @@ __global__ __launch_bounds__(1024) void pointwise_loss_vec_kernel(const uint4* _
     }
   }
   const float s = block_sum_1024(acc, sh);
-  if (threadIdx.x == 0) loss[blockIdx.x] = s * invR;
+  if (threadIdx.x == 0) reinterpret_cast<float*>(dpred + (int64_t)b * vec_per_row)[blockIdx.x] = s;
+}
+
+// second stage: one wavefront per model adds the chunk sums in order
+__global__ __launch_bounds__(64) void pointwise_loss_final_kernel(const uint4* __restrict__ dpred, float* __restrict__ loss,
+                                                                 int64_t vec_per_row, float invR) {
+  if (threadIdx.x != 0) return;
+  const float* part = reinterpret_cast<const float*>(dpred + (int64_t)blockIdx.x * vec_per_row);
+  float s = 0.f;
+  for (int i = 0; i < POINTWISE_CHUNKS; ++i) s += part[i];
+  loss[blockIdx.x] = s * invR;
 }
 
 // rows at least this long take the two-launch form when they are contiguous and 16-byte aligned
@@ -607,18 +625,23 @@ template <int KIND>
 static bool launch_pointwise_wide(int B, int64_t R, int dtype, const void* pred, const void* target, float* loss,
                                   void* dpred, int64_t sb, int64_t sr, hipStream_t st) {
   const int per = dtype == HFTA_BF16 ? 8 : 4;
-  if (sr != 1 || sb != R || R < POINTWISE_WIDE_MIN_R || R % per != 0 || !al16(pred) || !al16(target) || !al16(dpred))
+  if (sr != 1 || sb != R || R < POINTWISE_WIDE_MIN_R || R % per != 0 || !al16(pred) || !al16(target) || !al16(dpred) ||
+      dpred == pred || dpred == target || B > 65535)
     return false;
   const int64_t vpr = R / per, nvec = vpr * B;
   const float invR = 1.f / (float)R;
   const uint4* p4 = (const uint4*)pred; const uint4* t4 = (const uint4*)target; uint4* d4 = (uint4*)dpred;
-  if (dtype == HFTA_BF16) {
+  // loss first (its partial sums pass through dpred), then the gradient over the whole of dpred
+  const dim3 pg(POINTWISE_CHUNKS, (unsigned)B);
+  if (dtype == HFTA_BF16)
+    hipLaunchKernelGGL((pointwise_loss_part_kernel<bf16_raw, KIND>), pg, dim3(1024), 0, st, p4, t4, d4, vpr);
+  else
+    hipLaunchKernelGGL((pointwise_loss_part_kernel<float, KIND>), pg, dim3(1024), 0, st, p4, t4, d4, vpr);
+  hipLaunchKernelGGL(pointwise_loss_final_kernel, dim3((unsigned)B), dim3(64), 0, st, (const uint4*)d4, loss, vpr, invR);
+  if (dtype == HFTA_BF16)
     hipLaunchKernelGGL((pointwise_grad_vec_kernel<bf16_raw, KIND>), dim3(stream_blocks(nvec)), dim3(256), 0, st, p4, t4, d4, nvec, invR);
-    hipLaunchKernelGGL((pointwise_loss_vec_kernel<bf16_raw, KIND>), dim3((unsigned)B), dim3(1024), 0, st, p4, t4, loss, vpr, invR);
-  } else {
+  else
     hipLaunchKernelGGL((pointwise_grad_vec_kernel<float, KIND>), dim3(stream_blocks(nvec)), dim3(256), 0, st, p4, t4, d4, nvec, invR);
-    hipLaunchKernelGGL((pointwise_loss_vec_kernel<float, KIND>), dim3((unsigned)B), dim3(1024), 0, st, p4, t4, loss, vpr, invR);
-  }
   return true;
 }
 
