@@ -131,6 +131,11 @@ def test_conv1x1_fwd_bwd(hb, dtype, B, Nb, Ci, Co, L):
     Y = empty((Nb, B * Co, L), dtype)
     hb.conv1x1_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Bi, Y, ys)
     check(host(Y), oa.conv1x1_fwd(B, x, w, b), TOL[dtype], "Y")
+    # fused activation epilogue (select kind), with and without the bias
+    hb.conv1x1_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Bi, Y, ys, hb.ACT_LEAKY, 0.2)
+    check(host(Y), oops.act_fwd(oa.conv1x1_fwd(B, x, w, b), oops.ACT_LEAKY, 0.2), TOL[dtype], "leaky(Y)")
+    hb.conv1x1_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, None, Y, ys, hb.ACT_RELU)
+    check(host(Y), oops.act_fwd(oa.conv1x1_fwd(B, x, w, None), oops.ACT_RELU), TOL[dtype], "relu(Y, no bias)")
     dX = empty((Nb, B * Ci, L), dtype)
     dW = empty((B * Co, Ci), torch.float32)
     db = empty((B * Co,), torch.float32)
