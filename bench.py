@@ -191,11 +191,6 @@ def big_splits(G, M, N, K, S=1):
     return best
 
 
-def big_gemm_split(G, M, N, K, S=1):
-    """Weight-gradient shapes that run (possibly split over k) on the 256x256-tile kernel."""
-    return big_splits(G, M, N, K, S) > 0
-
-
 def algorithmic_flops(name, a):
     if name in ("linear_fwd", "linear_fwd_ws", "linear_bwd"):
         B, M, Fx, Fy = a[:4]

@@ -10,9 +10,14 @@
 // zeros, no memory request; see gemm_pf.h), so the hardware overlaps them with the MFMAs.
 // One workgroup per compute unit (147 KB LDS).  bf16 storage only.
 //
-// The epilogue is specialised at compile time (EPI_*): with one workgroup per compute unit
+// The epilogue is specialised at compile time (BIG_*): with one workgroup per compute unit
 // nothing overlaps it, and a run-time switch per element or an exact erf costs as much as the
 // k-loop of a K = 512 problem.
+//
+// Two kernels: gemm_big_kernel (one tile per workgroup; every epilogue kind) and, further down,
+// gemm_bigp_kernel (persistent: as many workgroups as compute units walk the tiles, with the
+// loads, the bias and the stores of neighbouring tiles overlapped; select-kind epilogues), which
+// the launcher takes whenever a launch has more tiles than compute units.
 #pragma once
 #include "gemm_pf.h"
 
