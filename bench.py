@@ -35,7 +35,7 @@ class Tracer:
 
     SINGLE_KERNEL = ("conv1x1_fwd", "conv1x1_bwd", "bn_fwd", "bn_bwd", "maxpool_points", "maxpool_points_bwd",
                      "adam_step_multi", "linear_fwd", "linear_fwd_ws", "linear_bwd", "bn_fwd_maxpool", "bn_bwd_maxpool",
-                     "act_fwd", "act_bwd", "act_bwd_colsum", "add", "layernorm_fwd", "layernorm_bwd",
+                     "act_fwd", "act_bwd", "act_bwd_colsum", "add", "layernorm_fwd", "layernorm_bwd", "layernorm_bwd_sums",
                      "conv2d_grouped_fwd", "conv2d_grouped_bwd", "bias_act_nchw", "conv1x1_bn_maxpool_fwd",
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
                      "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
@@ -113,6 +113,8 @@ def kernel_label(name, a):
             sp = big_splits(B, Fx, Fy, M) if dt == 1 else 0
             return (big_name(B, Fx, Fy, sp) if sp else "gemm_pf_kernel") + "(dW)"
         return "colsum_kernel"
+    if name == "layernorm_bwd_sums":
+        return "layernorm_bwd_kernel"
     if name in ("act_fwd", "act_bwd", "act_bwd_colsum", "add", "layernorm_fwd", "layernorm_bwd", "bias_act_nchw"):
         return name + "_kernel"
     if name in ("attention_fwd", "attention_bwd"):
@@ -300,6 +302,8 @@ def algorithmic_bytes(name, a):
         return 2 * a[0] * a[1] * a[2] * _es(a[3])
     if name == "layernorm_bwd":
         return 3 * a[0] * a[1] * a[2] * _es(a[3])
+    if name == "layernorm_bwd_sums":          # x, dy (and dy2) in, dx out
+        return (4 if a[6] is not None else 3) * a[0] * a[1] * a[2] * _es(a[3])
     if name == "maxpool_points":
         B, Nb, C, L, dt = a[:5]
         return B * Nb * C * (L * _es(dt) + _es(dt) + 4)

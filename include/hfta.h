@@ -453,6 +453,20 @@ size_t hfta_layernorm_bwd_workspace_bytes(int B, int R, int E);
 int hfta_layernorm_bwd(int B, int R, int E, int dtype, const void* X, const void* dY, const float* w,
                        const float* save_mean, const float* save_invstd,
                        void* dX, float* dw, float* db, void* workspace, size_t ws_bytes, void* stream);
+/* hfta_layernorm_bwd for a residual block y = LN(x + f(x)) (fusion rules table, LayerNorm and Linear
+ * rows), with the two reductions that otherwise take passes of their own over [B][R][E]:
+ *   the incoming gradient is dY + dY2 (dY2 may be NULL; the sum is rounded to the storage dtype as
+ *   a stored element-wise sum would be), and
+ *   dx_colsum[b][e] = sum over rows of dX[b][r][e] as stored (fp32 [B][E]): the bias gradient of the
+ *   Linear whose output entered the LayerNorm's input.
+ * Other arguments as hfta_layernorm_bwd; workspace hfta_layernorm_bwd_sums_workspace_bytes.
+ * EUNSUPPORTED unless X, dY, dY2, dX are 16-byte aligned and E is a multiple of the 16-byte piece
+ * with at most 128 pieces per row (use the separate calls then). */
+size_t hfta_layernorm_bwd_sums_workspace_bytes(int B, int R, int E);
+int hfta_layernorm_bwd_sums(int B, int R, int E, int dtype, const void* X, const void* dY, const void* dY2,
+                            const float* w, const float* save_mean, const float* save_invstd,
+                            void* dX, float* dw, float* db, float* dx_colsum,
+                            void* workspace, size_t ws_bytes, void* stream);
 /* Per-model losses with mean reduction over the model's own R rows; loss: fp32 [B];
  * dlogits in storage dtype.  No factor B appears because each model's loss is its
  * own mean (appendix "Fused Loss", eq. 3). */

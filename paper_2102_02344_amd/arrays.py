@@ -504,7 +504,8 @@ class FusedMlp(ParamArena):
         self.dE = [torch.empty(B, R, E, **act) for _ in range(3)]
         self.dH = [torch.empty(B, R, H, **act) for _ in range(2)]
         self.loss = torch.empty(B, **f32)
-        ws = max(4, hb.layernorm_bwd_workspace_bytes(B, R, E), hb.linear_bwd_workspace_bytes(B, R, E, H, self.dt),
+        ws = max(4, hb.layernorm_bwd_workspace_bytes(B, R, E), hb.layernorm_bwd_sums_workspace_bytes(B, R, E),
+                 hb.linear_bwd_workspace_bytes(B, R, E, H, self.dt),
                  hb.linear_bwd_workspace_bytes(B, R, H, E, self.dt))
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
 
@@ -531,39 +532,52 @@ class FusedMlp(ParamArena):
         d = self.dE[0]
         hb.mse(B, R * E, dt, self.x[nb], self.target, self.loss, d)
         P("mse", pred=self.x[nb], target=self.target, loss=self.loss, d=d)
-        cur = 0
+        # A block's incoming gradient is the pair (ga, gb) whose sum it is: the LayerNorm backward adds
+        # them on load (no stored sum) and also emits the column sums of its result, the second
+        # Linear's bias gradient.  (Rows of E that are not whole 16-byte pieces: the separate calls.)
+        epv = 8 if dt == hb.BF16 else 4
+        fused_ln = E % epv == 0 and E // epv <= 128
+        ga, gb, free = self.dE[0], None, [self.dE[1], self.dE[2]]
         for i in reversed(range(nb)):
             k = f"blk{i}"
-            ds, dxl = self.dE[(cur + 1) % 3], self.dE[(cur + 2) % 3]
-            hb.layernorm_bwd(B, R, E, dt, self.s[i], d, self.master(k + ".ln.w"), self.ln_mean[i], self.ln_invstd[i],
-                             ds, self.g(k + ".ln.w"), self.g(k + ".ln.b"), self.ws)
-            P("layernorm_bwd", layer=k, x=self.s[i], dy=d, w=self.master(k + ".ln.w"), mean=self.ln_mean[i],
-              invstd=self.ln_invstd[i], dx=ds, dw=self.g(k + ".ln.w"), db=self.g(k + ".ln.b"))
-            # data gradient, weight gradient and bias gradient as separate calls (one kernel each),
-            # so a caller can time them separately
+            ds = free.pop()
+            if fused_ln:
+                hb.layernorm_bwd_sums(B, R, E, dt, self.s[i], ga, gb, self.master(k + ".ln.w"), self.ln_mean[i],
+                                      self.ln_invstd[i], ds, self.g(k + ".ln.w"), self.g(k + ".ln.b"), self.g(k + ".b2"),
+                                      self.ws)
+            else:
+                if gb is not None:
+                    hb.add(B * R * E, dt, ga, gb, ga)
+                hb.layernorm_bwd(B, R, E, dt, self.s[i], ga, self.master(k + ".ln.w"), self.ln_mean[i], self.ln_invstd[i],
+                                 ds, self.g(k + ".ln.w"), self.g(k + ".ln.b"), self.ws)
+                hb.linear_bwd(B, R, H, E, dt, None, None, ds, None, None, self.g(k + ".b2"), None)
+            P("layernorm_bwd", layer=k, x=self.s[i], dy=ga, dy2=gb if fused_ln else None, w=self.master(k + ".ln.w"),
+              mean=self.ln_mean[i], invstd=self.ln_invstd[i], dx=ds, dw=self.g(k + ".ln.w"), db=self.g(k + ".ln.b"))
+            # data gradient and weight gradient as separate calls (one kernel each), so a caller can
+            # time them separately
             hb.linear_bwd(B, R, H, E, dt, None, self.w(k + ".w2"), ds, self.dH[0], None, None, None)
             hb.linear_bwd(B, R, H, E, dt, self.h[i], None, ds, None, self.g(k + ".w2"), None, self.ws)
-            hb.linear_bwd(B, R, H, E, dt, None, None, ds, None, None, self.g(k + ".b2"), None)
             P("linear_bwd", layer=k + ".2", x=self.h[i], w=self.w(k + ".w2"), dy=ds, dx=self.dH[0],
               dw=self.g(k + ".w2"), db=self.g(k + ".b2"))
             # GELU backward and the first Linear's bias gradient (column sums of its result) in one pass
             # (whole 16-byte pieces along H; otherwise the two separate calls)
-            if H % (8 if dt == hb.BF16 else 4) == 0:
+            if H % epv == 0:
                 hb.act_bwd_colsum(B, R, H, dt, self.u[i], self.dH[0], self.dH[1], self.g(k + ".b1"), hb.ACT_GELU)
             else:
                 hb.act_bwd(B * R * H, dt, self.u[i], self.dH[0], self.dH[1], hb.ACT_GELU)
                 hb.linear_bwd(B, R, E, H, dt, None, None, self.dH[1], None, None, self.g(k + ".b1"), None)
             P("act_bwd", layer=k, x=self.u[i], dy=self.dH[0], dx=self.dH[1], act=hb.ACT_GELU)
-            # nothing consumes the gradient of the array's input: the first block computes neither the
-            # data gradient of its first Linear nor the sum that would carry it further
+            # nothing consumes the gradient of the array's input: the first block computes no data
+            # gradient of its first Linear
+            dxl = ga                                   # this block's incoming gradient is dead: reuse it
             if i > 0:
                 hb.linear_bwd(B, R, E, H, dt, None, self.w(k + ".w1"), self.dH[1], dxl, None, None, None)
             hb.linear_bwd(B, R, E, H, dt, self.x[i], None, self.dH[1], None, self.g(k + ".w1"), None, self.ws)
             P("linear_bwd", layer=k + ".1", x=self.x[i], w=self.w(k + ".w1"), dy=self.dH[1], dx=dxl if i > 0 else None,
               dw=self.g(k + ".w1"), db=self.g(k + ".b1"))
-            if i > 0:
-                hb.add(B * R * E, dt, ds, dxl, d)      # d (this block's incoming gradient) is dead: reuse it
-                P("add", a=ds, b=dxl, y=d)
+            if gb is not None:
+                free.append(gb)
+            ga, gb = ds, dxl                           # the next block down receives ds + dxl
         return self.loss
 
 

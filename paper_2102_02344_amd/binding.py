@@ -93,6 +93,8 @@ _SIGS = {
     "hfta_layernorm_fwd": (_i, [_i, _i, _i, _i, _p, _p, _p, _f, _p, _p, _p, _p]),
     "hfta_layernorm_bwd_workspace_bytes": (_sz, [_i, _i, _i]),
     "hfta_layernorm_bwd": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
+    "hfta_layernorm_bwd_sums_workspace_bytes": (_sz, [_i, _i, _i]),
+    "hfta_layernorm_bwd_sums": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_softmax_xent": (_i, [_i, _i, _i, _i, _p, _p, _p, _p, _p]),
     "hfta_bce_logits": (_i, [_i, _i64, _i, _p, _p, _p, _p, _p]),
     "hfta_bce_logits_strided": (_i, [_i, _i64, _i, _p, _p, _p, _p, _i64, _i64, _p]),
@@ -350,6 +352,18 @@ def layernorm_bwd(B, R, E, dtype, X, dY, w, save_mean, save_invstd, dX, dw, db, 
     wp, wb = _ws(workspace)
     _check(_lib.hfta_layernorm_bwd(B, R, E, dtype, _ptr(X), _ptr(dY), _ptr(w), _ptr(save_mean), _ptr(save_invstd),
                                    _ptr(dX), _ptr(dw), _ptr(db), wp, wb, _stream(stream)), "hfta_layernorm_bwd")
+
+
+def layernorm_bwd_sums_workspace_bytes(B, R, E) -> int:
+    return _lib.hfta_layernorm_bwd_sums_workspace_bytes(B, R, E)
+
+
+def layernorm_bwd_sums(B, R, E, dtype, X, dY, dY2, w, save_mean, save_invstd, dX, dw, db, dx_colsum, workspace=None,
+                       stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_layernorm_bwd_sums(B, R, E, dtype, _ptr(X), _ptr(dY), _ptr(dY2), _ptr(w), _ptr(save_mean),
+                                        _ptr(save_invstd), _ptr(dX), _ptr(dw), _ptr(db), _ptr(dx_colsum), wp, wb,
+                                        _stream(stream)), "hfta_layernorm_bwd_sums")
 
 
 def softmax_xent(B, R, K, dtype, logits, labels, loss, dlogits, stream=None):

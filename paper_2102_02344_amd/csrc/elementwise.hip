@@ -243,18 +243,22 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict_
   }
 }
 
+// np = 2: [dw | db] partial rows per block; np = 3: a third row, the column sums of the stored dX
 __global__ __launch_bounds__(256) void layernorm_bwd_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
-                                                                  float* __restrict__ db, int E, int nblk) {
+                                                                  float* __restrict__ db, float* __restrict__ dxs, int E,
+                                                                  int nblk, int np) {
   const int b = blockIdx.y;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= E) return;
-  float aw = 0.f, ab = 0.f;
+  float aw = 0.f, ab = 0.f, ax = 0.f;
   for (int k = 0; k < nblk; ++k) {
-    const float* pw = part + (((int64_t)b * nblk + k) * 2) * E;
+    const float* pw = part + (((int64_t)b * nblk + k) * np) * E;
     aw += pw[e]; ab += pw[E + e];
+    if (np == 3) ax += pw[2 * E + e];
   }
   dw[(int64_t)b * E + e] = aw;
   db[(int64_t)b * E + e] = ab;
+  if (np == 3) dxs[(int64_t)b * E + e] = ax;
 }
 
 // ---- LayerNorm, register-resident rows ----------------------------------------
@@ -307,19 +311,24 @@ __global__ __launch_bounds__(256) void layernorm_fwd_vec_kernel(const uint4* __r
   }
 }
 
-template <typename T, int CH>
+// SUMS: the incoming gradient is dY + dY2 (rounded to the storage type, as if a separate element-wise
+// sum had stored it) when dY2 is given, and a third partial row carries the column sums of the
+// stored dX (the bias gradient of the Linear that produced X's residual branch).
+template <typename T, int CH, bool SUMS = false>
 __global__ __launch_bounds__(256) void layernorm_bwd_vec_kernel(const uint4* __restrict__ X, const uint4* __restrict__ dY,
                                                                const float* __restrict__ w, const float* __restrict__ save_mean,
                                                                const float* __restrict__ save_invstd, uint4* __restrict__ dX,
-                                                               float* __restrict__ part, int R, int E, int rows_per_block) {
+                                                               float* __restrict__ part, int R, int E, int rows_per_block,
+                                                               const uint4* __restrict__ dY2 = nullptr) {
   constexpr int N = V16<T>::N;
-  __shared__ float red[3][2][CH * 64 * N];                // waves 1..3: [dw | db] partials
+  constexpr int NP = SUMS ? 3 : 2;
+  __shared__ float red[3][NP][CH * 64 * N];               // waves 1..3: [dw | db (| dx sums)] partials
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int b = blockIdx.y;
   const int r_begin = blockIdx.x * rows_per_block;
   const int r_end = min(R, r_begin + rows_per_block);
   const int vpr = E / N;
-  float wl[CH][N], aw[CH][N], ab[CH][N];
+  float wl[CH][N], aw[CH][N], ab[CH][N], ax[SUMS ? CH : 1][N];
 #pragma unroll
   for (int c = 0; c < CH; ++c)
 #pragma unroll
@@ -327,6 +336,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_vec_kernel(const uint4* __r
       const int col = (lane + 64 * c) * N + e;
       wl[c][e] = col < E ? w[(int64_t)b * E + col] : 0.f;
       aw[c][e] = 0.f; ab[c][e] = 0.f;
+      if (SUMS) ax[c][e] = 0.f;
     }
   for (int r = r_begin + wv; r < r_end; r += 4) {
     const int64_t row = (int64_t)b * R + r;
@@ -340,6 +350,13 @@ __global__ __launch_bounds__(256) void layernorm_bwd_vec_kernel(const uint4* __r
         float x[N], d[N];
         V16<T>::unpack(X[row * vpr + v], x);
         V16<T>::unpack(dY[row * vpr + v], d);
+        if (SUMS && dY2) {
+          float d2[N];
+          V16<T>::unpack(dY2[row * vpr + v], d2);
+#pragma unroll
+          for (int e = 0; e < N; ++e) d[e] += d2[e];
+          V16<T>::unpack(V16<T>::pack(d), d);
+        }
 #pragma unroll
         for (int e = 0; e < N; ++e) {
           xh[c][e] = (x[e] - mean) * invstd;
@@ -358,7 +375,13 @@ __global__ __launch_bounds__(256) void layernorm_bwd_vec_kernel(const uint4* __r
         float o[N];
 #pragma unroll
         for (int e = 0; e < N; ++e) o[e] = invstd * (g[c][e] - s1 - xh[c][e] * s2);
-        dX[row * vpr + v] = V16<T>::pack(o);
+        const uint4 st = V16<T>::pack(o);
+        dX[row * vpr + v] = st;
+        if (SUMS) {
+          V16<T>::unpack(st, o);
+#pragma unroll
+          for (int e = 0; e < N; ++e) ax[c][e] += o[e];
+        }
       }
     }
   }
@@ -369,11 +392,12 @@ __global__ __launch_bounds__(256) void layernorm_bwd_vec_kernel(const uint4* __r
       for (int e = 0; e < N; ++e) {
         red[wv - 1][0][(lane + 64 * c) * N + e] = aw[c][e];
         red[wv - 1][1][(lane + 64 * c) * N + e] = ab[c][e];
+        if (SUMS) red[wv - 1][NP - 1][(lane + 64 * c) * N + e] = ax[c][e];
       }
   }
   __syncthreads();
   if (wv == 0) {
-    float* pw = part + (((int64_t)b * gridDim.x + blockIdx.x) * 2) * E;
+    float* pw = part + (((int64_t)b * gridDim.x + blockIdx.x) * NP) * E;
 #pragma unroll
     for (int c = 0; c < CH; ++c)
 #pragma unroll
@@ -382,6 +406,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_vec_kernel(const uint4* __r
         if (col < E) {
           pw[col] = ((aw[c][e] + red[0][0][col]) + red[1][0][col]) + red[2][0][col];
           pw[E + col] = ((ab[c][e] + red[0][1][col]) + red[1][1][col]) + red[2][1][col];
+          if (SUMS) pw[2 * E + col] = ((ax[c][e] + red[0][NP - 1][col]) + red[1][NP - 1][col]) + red[2][NP - 1][col];
         }
       }
   }
@@ -864,7 +889,39 @@ int hfta_layernorm_bwd(int B, int R, int E, int dtype, const void* X, const void
                        save_invstd, (float*)dX, (float*)workspace, R, E, rpb);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   hipLaunchKernelGGL(layernorm_bwd_reduce_kernel, dim3((unsigned)((E + 255) / 256), (unsigned)B), dim3(256), 0, st,
-                     (const float*)workspace, dw, db, E, nblk);
+                     (const float*)workspace, dw, db, (float*)nullptr, E, nblk, 2);
+  return launch_status();
+}
+
+size_t hfta_layernorm_bwd_sums_workspace_bytes(int B, int R, int E) {
+  if (B <= 0 || R <= 0 || E <= 0) return 0;
+  return (size_t)B * ln_blocks(R) * 3 * (size_t)E * sizeof(float);
+}
+
+int hfta_layernorm_bwd_sums(int B, int R, int E, int dtype, const void* X, const void* dY, const void* dY2, const float* w,
+                            const float* save_mean, const float* save_invstd, void* dX, float* dw, float* db,
+                            float* dx_colsum, void* workspace, size_t ws_bytes, void* stream) {
+  if (B <= 0 || R <= 0 || E <= 0 || !valid_dtype(dtype) || !X || !dY || !w || !save_mean || !save_invstd || !dX || !dw ||
+      !db || !dx_colsum)
+    return HFTA_EINVAL;
+  if (B > 65535) return HFTA_EUNSUPPORTED;
+  if (!workspace || ws_bytes < hfta_layernorm_bwd_sums_workspace_bytes(B, R, E)) return HFTA_EWORKSPACE;
+  const int epv = 16 / (int)dtype_size(dtype);
+  if (!(al16(X) && al16(dY) && al16(dX) && (!dY2 || al16(dY2)) && E % epv == 0 && E / epv <= 128)) return HFTA_EUNSUPPORTED;
+  const int nblk = ln_blocks(R);
+  const int rpb = (R + nblk - 1) / nblk;
+  hipStream_t st = as_stream(stream);
+  dim3 grid((unsigned)nblk, (unsigned)B);
+  const bool one = E / epv <= 64;
+  float* part = (float*)workspace;
+#define HFTA_LNS(T, CHN) hipLaunchKernelGGL((layernorm_bwd_vec_kernel<T, CHN, true>), grid, dim3(256), 0, st, (const uint4*)X, \
+    (const uint4*)dY, w, save_mean, save_invstd, (uint4*)dX, part, R, E, rpb, (const uint4*)dY2)
+  if (dtype == HFTA_BF16) { if (one) HFTA_LNS(bf16_raw, 1); else HFTA_LNS(bf16_raw, 2); }
+  else { if (one) HFTA_LNS(float, 1); else HFTA_LNS(float, 2); }
+#undef HFTA_LNS
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  hipLaunchKernelGGL(layernorm_bwd_reduce_kernel, dim3((unsigned)((E + 255) / 256), (unsigned)B), dim3(256), 0, st,
+                     (const float*)workspace, dw, db, dx_colsum, E, nblk, 3);
   return launch_status();
 }
 

@@ -51,7 +51,10 @@ def probe_for(spec, seen):
                 check(H64(kw["d"])[b], d, tol, "mse grad")
         elif op == "layernorm_bwd":
             E = kw["x"].shape[2]
-            dx, dw, db = oa.layernorm_bwd(B, H64(kw["x"]), H64(kw["dy"]), H64(kw["w"]).reshape(B, E),
+            dy = H64(kw["dy"])
+            if kw.get("dy2") is not None:     # the incoming gradient is a pair summed on load, as a stored sum would be
+                dy = oops.store(dy + H64(kw["dy2"]), spec.dtype)
+            dx, dw, db = oa.layernorm_bwd(B, H64(kw["x"]), dy, H64(kw["w"]).reshape(B, E),
                                           H64(kw["mean"]).reshape(B, -1), H64(kw["invstd"]).reshape(B, -1))
             check(H64(kw["dx"]), dx, tol, f"{lay} ln dx")
             check(H64(kw["dw"]).reshape(B, E), dw, 1e-5 if spec.dtype == "f32" else 2e-4, f"{lay} ln dw")
@@ -80,7 +83,7 @@ def test_every_call_in_place(dtype):
     seen = []
     arr.forward_backward(probe_for(spec, seen))
     assert seen.count("linear_fwd") == 2 * spec.blocks and seen.count("linear_bwd") == 2 * spec.blocks
-    assert seen.count("layernorm_bwd") == spec.blocks and seen.count("add") == 2 * spec.blocks - 1
+    assert seen.count("layernorm_bwd") == spec.blocks and seen.count("add") == spec.blocks
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -93,6 +96,7 @@ def test_free_running_steps_match_the_oracle(dtype):
     calls = 9 * spec.blocks + 1
     tol = (1e-5 if dtype == "f32" else 2e-2) * (calls if dtype == "f32" else 3)
     for t in (1, 2):
+        prev = [{n: np.array(v, np.float64) for n, v in st["theta"].items()} for st in states]
         outs = omlp.array_train_step(spec, states, inp, t)
         arr.forward_backward()
         torch.cuda.synchronize()
@@ -111,7 +115,10 @@ def test_free_running_steps_match_the_oracle(dtype):
             for name, _ in arr.shapes:
                 th = arr.param_host(arr.theta, name, b).astype(np.float64)
                 ref = states[b]["theta"][name].astype(np.float64)
-                gref = outs[b]["grads"][name]
+                # Adam divides by the magnitude of what it is given, the gradient plus weight decay times
+                # the parameter: where those two cancel, a last-bit difference in the gradient moves the
+                # step by percents, so such elements are left to the looser bound below
+                gref = outs[b]["grads"][name] + float(inp["wd"][b]) * prev[b][name].reshape(outs[b]["grads"][name].shape)
                 ok = np.abs(gref) >= 1e-2 * np.abs(gref).max()
                 assert np.abs(th - ref)[ok].max() <= max(tol * np.abs(ref).max(), 10 * tol * lr * t), (name, b, t)
                 assert np.abs(th - ref).max() <= 2.5 * lr * t, (name, b, t)

@@ -457,7 +457,7 @@ def test_activations_dropout(hb, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("B,R,E", [(3, 200, 512), (2, 7, 100)])
+@pytest.mark.parametrize("B,R,E", [(3, 200, 512), (2, 7, 100), (2, 300, 1016)])
 def test_layernorm(hb, dtype, B, R, E):
     x = hi.snap(hi.normal(81, (B, R, E)) * 2 + 0.5, dtype)
     w, b = hi.normal(82, (B, E)) * 0.5 + 1.0, hi.normal(83, (B, E)) * 0.2
@@ -477,6 +477,24 @@ def test_layernorm(hb, dtype, B, R, E):
     check(host(dX), rdx, TOL[dtype], "dX")
     check(host(dw), rdw, f32_tol(dtype), "dw")
     check(host(db), rdb, f32_tol(dtype), "db")
+    # the residual-block form: gradient given as a pair summed on load, column sums of dX on the side
+    ws = torch.empty(hb.layernorm_bwd_sums_workspace_bytes(B, R, E), dtype=torch.uint8, device="cuda")
+    dy2 = hi.normal(85, (B, R, E), dtype)
+    dxs = empty((B, E), torch.float32)
+    epv = 8 if dtype == "bf16" else 4
+    if E % epv != 0 or E // epv > 128:         # not a row of at most 128 whole 16-byte pieces: unsupported
+        with pytest.raises(RuntimeError):
+            hb.layernorm_bwd_sums(B, R, E, DT[dtype], X, dY, dev(dy2, dtype), Wt, SM, SI, dX, dw, db, dxs, ws)
+        return
+    for second in (dy2, None):
+        hb.layernorm_bwd_sums(B, R, E, DT[dtype], X, dY, None if second is None else dev(second, dtype), Wt, SM, SI, dX, dw,
+                              db, dxs, ws)
+        dsum = dy if second is None else oops.store(dy.astype(np.float64) + second, dtype)
+        rdx, rdw, rdb = oa.layernorm_bwd(B, x, dsum, w, rmean, rinv)
+        check(host(dX), rdx, TOL[dtype], "dX (sums)")
+        check(host(dw), rdw, f32_tol(dtype), "dw (sums)")
+        check(host(db), rdb, f32_tol(dtype), "db (sums)")
+        check(host(dxs), host(dX).astype(np.float64).sum(axis=1), f32_tol(dtype), "column sums of the stored dX")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
