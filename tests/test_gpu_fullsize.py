@@ -239,9 +239,61 @@ def test_c4_linear_full_size_sampled(Fx, Fy):
     b, r, i, j = (torch.from_numpy(rng.integers(0, m, S)).cuda() for m in (B, M, Fx, Fy))
     ref = (f64(X[b, r, :]) * f64(W[b, :, j])).sum(axis=1) + f64(bias[b, j])
     rel_ok(f64(Y[b, r, j]), oops.act_fwd(ref, oops.ACT_GELU), TOL["bf16"], "Y = gelu(XW + b)")
+    for act, oact in ((hb.ACT_NONE, oops.ACT_NONE), (hb.ACT_RELU, oops.ACT_RELU)):   # the persistent kernel's epilogues
+        hb.linear_fwd(B, M, Fx, Fy, DT["bf16"], X, W, bias, Y, act)
+        torch.cuda.synchronize()
+        rel_ok(f64(Y[b, r, j]), oops.act_fwd(ref, oact), TOL["bf16"], f"Y = act{act}(XW + b)")
     rel_ok(f64(dX[b, r, i]), (f64(dY[b, r, :]) * f64(W[b, i, :])).sum(axis=1), TOL["bf16"], "dX")
     rel_ok(f64(dW[b, i, j]), (f64(X[b, :, i]) * f64(dY[b, :, j])).sum(axis=1), 2e-4, "dW")
     rel_ok(f64(db), f64(dY).sum(axis=1), 2e-4, "dbias")
+
+
+def test_c4_fused_reductions_full_size():
+    """Config 4's element-wise operators with reductions folded in (GELU backward + bias gradient,
+    LayerNorm backward + residual sum + bias gradient), B=16 models x 4096 tokens, bf16: sampled
+    elements / rows by the oracle's definitions, the sums against the stored tensors."""
+    from paper_2102_02344_amd import binding as hb
+    B, R, E, H = 16, 4096, 512, 2048
+    g = torch.Generator(device="cuda").manual_seed(44)
+    Z = torch.randn(B, R, H, device="cuda", generator=g).to(bf)
+    dA = torch.randn(B, R, H, device="cuda", generator=g).to(bf)
+    dZ = torch.empty_like(Z)
+    db1 = torch.empty(B, H, device="cuda")
+    hb.act_bwd_colsum(B, R, H, DT["bf16"], Z, dA, dZ, db1, hb.ACT_GELU)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    S = 8192
+    b, r, j = (torch.from_numpy(rng.integers(0, m, S)).cuda() for m in (B, R, H))
+    rel_ok(f64(dZ[b, r, j]), oops.act_bwd(f64(Z[b, r, j]), f64(dA[b, r, j]), oops.ACT_GELU), TOL["bf16"], "gelu backward")
+    rel_ok(f64(db1), dZ.double().sum(dim=1).cpu().numpy(), 2e-4, "bias gradient = column sums of the stored dZ")
+    del Z, dA, dZ
+
+    X = (torch.randn(B, R, E, device="cuda", generator=g) * 2 + 0.5).to(bf)
+    w = torch.randn(B, E, device="cuda", generator=g) * 0.5 + 1.0
+    bt = torch.randn(B, E, device="cuda", generator=g) * 0.2
+    d1 = torch.randn(B, R, E, device="cuda", generator=g).to(bf)
+    d2 = torch.randn(B, R, E, device="cuda", generator=g).to(bf)
+    SM, SI = torch.empty(B, R, device="cuda"), torch.empty(B, R, device="cuda")
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    dw, db, dxs = (torch.empty(B, E, device="cuda") for _ in range(3))
+    ws = torch.empty(hb.layernorm_bwd_sums_workspace_bytes(B, R, E), dtype=torch.uint8, device="cuda")
+    hb.layernorm_fwd(B, R, E, DT["bf16"], X, w, bt, 1e-5, SM, SI, Y)
+    hb.layernorm_bwd_sums(B, R, E, DT["bf16"], X, d1, d2, w, SM, SI, dX, dw, db, dxs, ws)
+    torch.cuda.synchronize()
+    dsum = (d1.float() + d2.float()).to(bf)                 # the pair as a stored sum
+    for bb in (0, 7, 15):
+        rows = np.sort(rng.choice(R, 64, replace=False))
+        x = f64(X[bb, rows])
+        mean = x.mean(axis=1)
+        invstd = 1.0 / np.sqrt(x.var(axis=1) + 1e-5)
+        rel_ok(f64(SM[bb, rows]), mean, 1e-5, "row mean")
+        rel_ok(f64(SI[bb, rows]), invstd, 1e-5, "row 1/std")
+        rdx, _, _ = oops.layernorm_bwd(x, f64(dsum[bb, rows]), f64(w[bb]), mean, invstd)
+        rel_ok(f64(dX[bb, rows]), rdx, TOL["bf16"], "LayerNorm dX rows")
+    xhat = (X.double() - SM.double()[:, :, None]) * SI.double()[:, :, None]
+    rel_ok(f64(dw), (dsum.double() * xhat).sum(dim=1).cpu().numpy(), 2e-4, "LayerNorm dw")
+    rel_ok(f64(db), dsum.double().sum(dim=1).cpu().numpy(), 2e-4, "LayerNorm db")
+    rel_ok(f64(dxs), dX.double().sum(dim=1).cpu().numpy(), 2e-4, "column sums of the stored dX")
 
 
 @pytest.mark.parametrize("Ci,Co,H", [(64, 128, 32), (3, 64, 64)])
