@@ -135,6 +135,27 @@ def test_validation_of_the_wider_entry_points(lib):
     assert raw.hfta_steplr(4, one, one, one, -1, one, None) == lib.EINVAL
     assert raw.hfta_steplr(4, one, None, one, 3, one, None) == lib.EINVAL
 
+    # ---- element-wise backward operators with reductions folded in
+    assert raw.hfta_act_bwd_colsum(0, 64, 64, 1, one, one, one, one, 1, 0.0, None) == lib.EINVAL
+    assert raw.hfta_act_bwd_colsum(2, 64, 64, 1, one, None, one, one, 1, 0.0, None) == lib.EINVAL
+    assert raw.hfta_act_bwd_colsum(2, 64, 64, 1, one, one, one, None, 1, 0.0, None) == lib.EINVAL
+    assert raw.hfta_act_bwd_colsum(2, 64, 64, 1, one, one, one, one, 99, 0.0, None) == lib.EINVAL
+    assert raw.hfta_act_bwd_colsum(2, 64, 100, 1, one, one, one, one, 1, 0.0, None) == lib.EUNSUPPORTED   # 100 bf16: no whole pieces
+    assert raw.hfta_act_bwd_colsum(2, 64, 64, 1, C.c_void_p(264), one, one, one, 1, 0.0, None) == lib.EUNSUPPORTED  # 8-byte aligned
+    need = raw.hfta_layernorm_bwd_sums_workspace_bytes(2, 64, 512)
+    assert need > raw.hfta_layernorm_bwd_workspace_bytes(2, 64, 512) > 0
+
+    def ln_sums(B=2, E=512, X=one, dxs=one, ws=one, nws=need, dy2=None):
+        return raw.hfta_layernorm_bwd_sums(B, 64, E, 1, X, one, dy2, one, one, one, one, one, one, dxs, ws, nws, None)
+    assert ln_sums(B=0) == lib.EINVAL
+    assert ln_sums(X=None) == lib.EINVAL
+    assert ln_sums(dxs=None) == lib.EINVAL
+    assert ln_sums(ws=None) == lib.EWORKSPACE
+    assert ln_sums(nws=need - 1) == lib.EWORKSPACE
+    assert ln_sums(E=100, nws=1 << 30) == lib.EUNSUPPORTED            # 100 bf16: no whole pieces
+    assert ln_sums(E=2048, nws=1 << 30) == lib.EUNSUPPORTED           # more than 128 pieces per row
+    assert ln_sums(dy2=C.c_void_p(264)) == lib.EUNSUPPORTED           # second gradient only 8-byte aligned
+
     # ---- Embedding, attention core, wide-class cross-entropy, per-sample point transform
     assert raw.hfta_embedding_fwd(2, 64, 0, 32, 1, one, one, 1.0, None, 0, one, None) == lib.EINVAL
     assert raw.hfta_embedding_bwd(2, 7681, 100, 32, 1, one, one, 1.0, one, None) == lib.EUNSUPPORTED
