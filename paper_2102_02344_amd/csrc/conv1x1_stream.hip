@@ -33,16 +33,21 @@ struct StreamArgs {
   uint32_t w_extent, x_extent;
 };
 
-template <int KT>
-__global__ __launch_bounds__(GEMM_THREADS) void conv1x1_stream_kernel(StreamArgs p) {
+// ONE: the layer has a single 128-row W tile (Co <= 128), so the X tile is dead once the matrix
+// instructions have run and the output staging tile may lie over it: 37 KB of LDS instead of 52 KB
+// at KT = 64, i.e. four workgroups per compute unit instead of three (register budget via launch
+// bounds).
+template <int KT, bool ONE = false>
+__global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kernel(StreamArgs p) {
   constexpr int PITCH = KT * 2 + 16;                   // bytes per LDS row: KT bf16 + pad
   constexpr int TILE = 128 * PITCH;
   constexpr int STAGE = 128 * EPI_PITCH2;
   constexpr int SREG = TILE > STAGE ? TILE : STAGE;    // W tile, then the output staging tile
   constexpr int SUB = KT / 32;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[TILE + SREG];
-  unsigned char* Xs = smem;
-  unsigned char* Ws = smem + TILE;
+  constexpr int SMEM = ONE ? (2 * TILE > STAGE ? 2 * TILE : STAGE) : TILE + SREG;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  unsigned char* Xs = ONE ? smem + TILE : smem;        // ONE: [W tile | X tile], staging over both
+  unsigned char* Ws = ONE ? smem : smem + TILE;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -172,7 +177,8 @@ int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, cons
   }
   a.w_extent = (uint32_t)w_ext; a.x_extent = (uint32_t)x_ext;
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
-  if (Ci <= 64) hipLaunchKernelGGL(conv1x1_stream_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
+  if (Ci <= 64 && Co <= 128) hipLaunchKernelGGL((conv1x1_stream_kernel<64, true>), grid, dim3(GEMM_THREADS), 0, st, a);
+  else if (Ci <= 64) hipLaunchKernelGGL(conv1x1_stream_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
   else if (Ci <= 128) hipLaunchKernelGGL(conv1x1_stream_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);
   else hipLaunchKernelGGL(conv1x1_stream_kernel<256>, grid, dim3(GEMM_THREADS), 0, st, a);
   return launch_status();
