@@ -26,6 +26,24 @@ struct BnFwdArgs {
   float eps, momentum, slope;
 };
 
+// Walks the (sample n, chunk ch) pairs of one channel in steps of the workgroup size without a
+// division per step (a 64-bit quotient per element chunk cost more vector-ALU time than the loads
+// it addressed): the step is split once into whole rows and a remainder.
+struct RowWalk {
+  int n, ch, chunks, dn, dc;
+  __device__ __forceinline__ RowWalk(int chunks_, int nt) : chunks(chunks_) {
+    n = (int)threadIdx.x / chunks_;
+    ch = (int)threadIdx.x - n * chunks_;
+    dn = nt / chunks_;
+    dc = nt - dn * chunks_;
+  }
+  __device__ __forceinline__ void step() {
+    n += dn;
+    ch += dc;
+    if (ch >= chunks) { ch -= chunks; ++n; }
+  }
+};
+
 template <typename T, int VEC, int NT>
 __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
   __shared__ float sh[NT / 64][2];
@@ -33,11 +51,10 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
   const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
   T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
   const int chunks = p.L / VEC;
-  const int64_t total = (int64_t)p.Nb * chunks;
   const float shift = Elem<T>::load(x);
   float s1 = 0.f, s2 = 0.f;
-  for (int64_t i = threadIdx.x; i < total; i += NT) {
-    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
+    const int n = w.n, ch = w.ch;
     float v[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
 #pragma unroll
@@ -61,8 +78,8 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
       p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
     }
   }
-  for (int64_t i = threadIdx.x; i < total; i += NT) {
-    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
+    const int n = w.n, ch = w.ch;
     float v[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
 #pragma unroll
@@ -139,10 +156,9 @@ __global__ __launch_bounds__(NT) void bn_bwd_conv_kernel(BnBwdArgs p) {
   T* dx = reinterpret_cast<T*>(p.dX) + b * p.dxsb + c * p.dxsc;
   const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
   const int chunks = p.L / VEC;
-  const int64_t total = (int64_t)p.Nb * chunks;
   float s1 = 0.f, s2 = 0.f;
-  for (int64_t i = threadIdx.x; i < total; i += NT) {
-    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
+    const int n = w.n, ch = w.ch;
     float v[VEC], d[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
     load_vec<T, VEC>(dy + n * p.dysn + ch * VEC, d);
@@ -159,8 +175,8 @@ __global__ __launch_bounds__(NT) void bn_bwd_conv_kernel(BnBwdArgs p) {
   const float m = (float)p.Nb * (float)p.L;
   const float mb = s1 / m, mg = s2 / m, sc = g * invstd;
   float s3 = 0.f;
-  for (int64_t i = threadIdx.x; i < total; i += NT) {
-    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
+    const int n = w.n, ch = w.ch;
     float v[VEC], d[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
     load_vec<T, VEC>(dy + n * p.dysn + ch * VEC, d);
