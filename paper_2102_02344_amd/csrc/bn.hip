@@ -26,24 +26,6 @@ struct BnFwdArgs {
   float eps, momentum, slope;
 };
 
-// Walks the (sample n, chunk ch) pairs of one channel in steps of the workgroup size without a
-// division per step (a 64-bit quotient per element chunk cost more vector-ALU time than the loads
-// it addressed): the step is split once into whole rows and a remainder.
-struct RowWalk {
-  int n, ch, chunks, dn, dc;
-  __device__ __forceinline__ RowWalk(int chunks_, int nt) : chunks(chunks_) {
-    n = (int)threadIdx.x / chunks_;
-    ch = (int)threadIdx.x - n * chunks_;
-    dn = nt / chunks_;
-    dc = nt - dn * chunks_;
-  }
-  __device__ __forceinline__ void step() {
-    n += dn;
-    ch += dc;
-    if (ch >= chunks) { ch -= chunks; ++n; }
-  }
-};
-
 template <typename T, int VEC, int NT>
 __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
   __shared__ float sh[NT / 64][2];

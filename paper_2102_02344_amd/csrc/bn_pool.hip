@@ -39,9 +39,8 @@ __global__ __launch_bounds__(NT) void bn_fwd_maxpool_kernel(BnPoolFwdArgs p) {
   float s1 = 0.f, s2 = 0.f;
   // same element -> thread assignment and reduction order as the stand-alone BatchNorm forward,
   // so the statistics (and with them every activated value) come out bit-identical
-  const int64_t total = (int64_t)p.Nb * chunks;
-  for (int64_t i = threadIdx.x; i < total; i += NT) {
-    const int n = (int)(i / chunks), ch = (int)(i - (int64_t)n * chunks);
+  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
+    const int n = w.n, ch = w.ch;
     float v[VEC];
     load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
 #pragma unroll

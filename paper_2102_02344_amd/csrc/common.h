@@ -39,6 +39,24 @@ template <> struct Elem<bf16_raw> {
   static __device__ __forceinline__ bf16_raw from_f32(float v) { return f32_to_bf16(v); }
 };
 
+// Walks the (sample n, chunk ch) pairs of one channel in steps of the workgroup size without a
+// division per step (a 64-bit quotient per element chunk cost more vector-ALU time than the loads
+// it addressed): the step is split once into whole rows and a remainder.
+struct RowWalk {
+  int n, ch, chunks, dn, dc;
+  __device__ __forceinline__ RowWalk(int chunks_, int nt) : chunks(chunks_) {
+    n = (int)threadIdx.x / chunks_;
+    ch = (int)threadIdx.x - n * chunks_;
+    dn = nt / chunks_;
+    dc = nt - dn * chunks_;
+  }
+  __device__ __forceinline__ void step() {
+    n += dn;
+    ch += dc;
+    if (ch >= chunks) { ch -= chunks; ++n; }
+  }
+};
+
 __device__ __forceinline__ float apply_act(float x, int act, float slope) {
   switch (act) {
     case HFTA_ACT_RELU: return x > 0.f ? x : 0.f;
