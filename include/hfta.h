@@ -91,6 +91,23 @@ int hfta_linear_fwd_ws(int B, int M, int Fx, int Fy, int dtype,
                        const void* X, const void* W, const void* bias, void* Y,
                        int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
 
+/* hfta_linear_fwd_ws for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the split partials live in a device array
+ * of HFTA_LINEAR_FWD_STATIC_BYTES that is part of the library image, so the call takes no workspace
+ * and makes no allocation.  Same arguments, results and validation as hfta_linear_fwd_ws (bit-equal:
+ * same kernels, same split count).  HFTA_EWORKSPACE when the partials of the shape exceed the array
+ * (hfta_linear_fwd_workspace_bytes(...) > hfta_linear_fwd_static_max_bytes()); HFTA_ELAUNCH when the
+ * array's address cannot be obtained on the current device.  Every GPU the library runs on holds its
+ * own copy of the array until the process ends; its address is looked up once per device (the one
+ * piece of state the library keeps).  All calls on one GPU share the array: calls that overlap there
+ * (different streams or threads) race; calls on one stream do not.  Nothing in it needs clearing:
+ * each call writes every partial it later reads. */
+#define HFTA_LINEAR_FWD_STATIC_BYTES (8u << 20)
+size_t hfta_linear_fwd_static_max_bytes(void);
+int hfta_linear_fwd_static(int B, int M, int Fx, int Fy, int dtype,
+                           const void* X, const void* W, const void* bias, void* Y,
+                           int act, float act_slope, void* stream);
+
 /* Backward of hfta_linear_fwd with act = NONE (apply hfta_act_bwd first otherwise).
  *   dX[b] = dY[b] W[b]^T   (storage dtype; NULL = skip)
  *   dW[b] = X[b]^T dY[b]   (fp32 [B][Fx][Fy]; NULL = skip)

@@ -44,6 +44,8 @@ _SIGS = {
     "hfta_linear_fwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _i, _f, _p]),
     "hfta_linear_fwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
     "hfta_linear_fwd_ws": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _i, _f, _p, _sz, _p]),
+    "hfta_linear_fwd_static_max_bytes": (_sz, []),
+    "hfta_linear_fwd_static": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _i, _f, _p]),
     "hfta_linear_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
     "hfta_linear_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_conv1x1_fwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _s4, _i, _f, _p]),
@@ -165,6 +167,15 @@ def linear_fwd_ws(B, M, Fx, Fy, dtype, X, W, bias, Y, act=ACT_NONE, act_slope=0.
     wp, wb = _ws(workspace)
     _check(_lib.hfta_linear_fwd_ws(B, M, Fx, Fy, dtype, _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), act, act_slope,
                                    wp, wb, _stream(stream)), "hfta_linear_fwd_ws")
+
+
+def linear_fwd_static_max_bytes() -> int:
+    return _lib.hfta_linear_fwd_static_max_bytes()
+
+
+def linear_fwd_static(B, M, Fx, Fy, dtype, X, W, bias, Y, act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_linear_fwd_static(B, M, Fx, Fy, dtype, _ptr(X), _ptr(W), _ptr(bias), _ptr(Y), act, act_slope,
+                                       _stream(stream)), "hfta_linear_fwd_static")
 
 
 def linear_bwd_workspace_bytes(B, M, Fx, Fy, dtype) -> int:

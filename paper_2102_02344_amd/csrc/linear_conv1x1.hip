@@ -2,6 +2,7 @@
 // forward / data-gradient / weight-gradient forms onto the batched GEMM core,
 // plus the bias-gradient reductions.
 #include "gemm.h"
+#include <mutex>
 
 namespace hfta {
 int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
@@ -224,6 +225,28 @@ GemmDesc conv_dw_desc(int B, int Nb, int Ci, int Co, int L, int dtype, const voi
   return d;
 }
 
+// Built-in scratch of hfta_linear_fwd_static (split partials; every call on a GPU shares it).
+__device__ __align__(256) unsigned char scratch[HFTA_LINEAR_FWD_STATIC_BYTES];
+
+// Device address of `scratch` on the current device, looked up on the first call there.
+float* static_scratch() {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    ptr[dev] = q;
+  }
+  return reinterpret_cast<float*>(ptr[dev]);
+}
+
 }  // namespace
 
 extern "C" {
@@ -250,23 +273,16 @@ size_t hfta_linear_fwd_workspace_bytes(int B, int M, int Fx, int Fy, int dtype) 
   return splits > 1 ? (size_t)splits * B * M * Fy * sizeof(float) : 0;
 }
 
-int hfta_linear_fwd_ws(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* W, const void* bias,
-                       void* Y, int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
-  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !X || !W || !Y || !valid_dtype(dtype) || !valid_act(act))
-    return HFTA_EINVAL;
-  const int splits = linear_fwd_splits(B, M, Fx, Fy, dtype);
-  if (splits <= 1) return hfta_linear_fwd(B, M, Fx, Fy, dtype, X, W, bias, Y, act, act_slope, stream);
-  if (!fits_i32((int64_t)M * Fx) || !fits_i32((int64_t)M * Fy) || !fits_i32((int64_t)Fx * Fy)) return HFTA_EINVAL;
-  const size_t need = (size_t)splits * B * M * Fy * sizeof(float);
-  if (!workspace || ws_bytes < need) return HFTA_EWORKSPACE;
+// Split forward: fp32 partial products into `partial`, then the fixed-order sum with bias and act.
+static int linear_fwd_split(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* W, const void* bias,
+                            void* Y, int act, float act_slope, int splits, float* partial, hipStream_t st) {
   GemmDesc d = base_desc(dtype);
   d.A = X; d.Bm = W; d.C = nullptr;
   d.M = M; d.N = Fy; d.K = Fx; d.G0 = B;
   d.a_kc = true; d.a_ld = Fx; d.a_g0 = (int64_t)M * Fx;
   d.b_kc = false; d.b_ld = Fy; d.b_g0 = (int64_t)Fx * Fy;
   d.c_ld = Fy; d.c_g0 = (int64_t)M * Fy;
-  d.out_f32 = true; d.splits = splits; d.partial = reinterpret_cast<float*>(workspace); d.keep_partials = true;
-  hipStream_t st = as_stream(stream);
+  d.out_f32 = true; d.splits = splits; d.partial = partial; d.keep_partials = true;
   const int rc = gemm_launch(d, st);
   if (rc != HFTA_OK) return rc;
   const int64_t count = (int64_t)B * M * Fy;
@@ -278,6 +294,39 @@ int hfta_linear_fwd_ws(int B, int M, int Fx, int Fy, int dtype, const void* X, c
     hipLaunchKernelGGL(splitk_bias_act_kernel<float>, grid, dim3(256), 0, st, d.partial, (float*)Y,
                        (const float*)bias, count, M * Fy, Fy, splits, act, act_slope);
   return launch_status();
+}
+
+int hfta_linear_fwd_ws(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* W, const void* bias,
+                       void* Y, int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !X || !W || !Y || !valid_dtype(dtype) || !valid_act(act))
+    return HFTA_EINVAL;
+  const int splits = linear_fwd_splits(B, M, Fx, Fy, dtype);
+  if (splits <= 1) return hfta_linear_fwd(B, M, Fx, Fy, dtype, X, W, bias, Y, act, act_slope, stream);
+  if (!fits_i32((int64_t)M * Fx) || !fits_i32((int64_t)M * Fy) || !fits_i32((int64_t)Fx * Fy)) return HFTA_EINVAL;
+  const size_t need = (size_t)splits * B * M * Fy * sizeof(float);
+  if (!workspace || ws_bytes < need) return HFTA_EWORKSPACE;
+  return linear_fwd_split(B, M, Fx, Fy, dtype, X, W, bias, Y, act, act_slope, splits,
+                          reinterpret_cast<float*>(workspace), as_stream(stream));
+}
+
+// hfta_linear_fwd_ws for callers that cannot allocate: the split partials live in `scratch`, a
+// device array that is part of the library image.  In host code the array's name is only a
+// handle; the memory is reached through the address hipGetSymbolAddress returns, looked up once
+// per device (every GPU holds its own copy at its own address).
+size_t hfta_linear_fwd_static_max_bytes(void) { return HFTA_LINEAR_FWD_STATIC_BYTES; }
+
+int hfta_linear_fwd_static(int B, int M, int Fx, int Fy, int dtype, const void* X, const void* W, const void* bias,
+                           void* Y, int act, float act_slope, void* stream) {
+  if (B <= 0 || M <= 0 || Fx <= 0 || Fy <= 0 || !X || !W || !Y || !valid_dtype(dtype) || !valid_act(act))
+    return HFTA_EINVAL;
+  const int splits = linear_fwd_splits(B, M, Fx, Fy, dtype);
+  if (splits <= 1) return hfta_linear_fwd(B, M, Fx, Fy, dtype, X, W, bias, Y, act, act_slope, stream);
+  if (!fits_i32((int64_t)M * Fx) || !fits_i32((int64_t)M * Fy) || !fits_i32((int64_t)Fx * Fy)) return HFTA_EINVAL;
+  const size_t need = (size_t)splits * B * M * Fy * sizeof(float);
+  if (need > (size_t)HFTA_LINEAR_FWD_STATIC_BYTES) return HFTA_EWORKSPACE;   // beyond the built-in scratch
+  float* partial = static_scratch();
+  if (!partial) return HFTA_ELAUNCH;
+  return linear_fwd_split(B, M, Fx, Fy, dtype, X, W, bias, Y, act, act_slope, splits, partial, as_stream(stream));
 }
 
 size_t hfta_linear_bwd_workspace_bytes(int B, int M, int Fx, int Fy, int dtype) {

@@ -47,6 +47,12 @@ def test_validation_precedes_launch(lib):
     assert need > 0 and raw.hfta_linear_fwd_workspace_bytes(8, 128, 1024, 512, 1) == 0
     assert raw.hfta_linear_fwd_ws(8, 32, 1024, 512, 1, one, one, None, one, 0, 0.0, one, need - 1, None) == lib.EWORKSPACE
     assert raw.hfta_linear_fwd_ws(8, 32, 1024, 512, 1, one, None, None, one, 0, 0.0, one, need, None) == lib.EINVAL
+    # the entry point without a workspace: same validation; shapes whose partials exceed its built-in array
+    assert raw.hfta_linear_fwd_static_max_bytes() == 8 << 20
+    assert raw.hfta_linear_fwd_static(8, 32, 1024, 512, 1, one, None, None, one, 0, 0.0, None) == lib.EINVAL
+    assert raw.hfta_linear_fwd_static(0, 32, 1024, 512, 1, one, one, None, one, 0, 0.0, None) == lib.EINVAL
+    assert raw.hfta_linear_fwd_workspace_bytes(9, 64, 8192, 2048, 1) > 8 << 20
+    assert raw.hfta_linear_fwd_static(9, 64, 8192, 2048, 1, one, one, None, one, 0, 0.0, None) == lib.EWORKSPACE
     # stride_l != 1 is not implemented for the conv family
     assert raw.hfta_conv1x1_fwd(1, 2, 3, 4, 4, 0, one, bad_l, one, None, one, s4, 0, 0.0, None) == lib.EUNSUPPORTED
     assert raw.hfta_conv1x1_fwd(1, 2, 3, 4, 4, 0, one, None, one, None, one, s4, 0, 0.0, None) == lib.EINVAL
