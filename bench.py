@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused training array on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c0|c3|c4] [--skip-serial] [--skip-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--repeats R] [--workload all|c0|c1|c2|c3|c4|c1t|t0] [--skip-serial] [--skip-cpu]
 
 A step is one forward + backward + Adam pass of the whole fused array over one
 synthetic batch that is already resident in HBM.  Prints ONE JSON line:
@@ -536,19 +536,118 @@ class Workload:
                            f"{os.cpu_count()} logical cores")
 
 
+def _stats(xs):
+    return dict(mean=float(np.mean(xs)), min=float(np.min(xs)), max=float(np.max(xs)))
+
+
+def run_workload(name, args, torch, arrays, binding):
+    """All legs of one workload: fused (REPEATS timed regions of `steps` steps each), the same models
+    one after another with B = 1, the CPU oracle on a bounded sample, the per-entry table and the
+    roofline of the entry with the largest share of a step."""
+    wl = Workload(name)
+    spec, inp = wl.spec, wl.inp
+    tracer = Tracer(binding, torch)
+    arrays.hb = tracer
+    unf = args.unfused if name == "c1" else 0
+    arr = wl.cls(spec, inp, unfused_layers=tuple(range(unf))) if unf else wl.cls(spec, inp)
+    if unf:
+        wl.config["unfused_per_point_layers"] = unf
+    # Warm-up.  Its last steps bracket EVERY traced entry point with HIP events: the per-kernel table,
+    # and which entry has the largest share of a step.  (Two events per call cost host time, about
+    # as much as a whole step of config 1 for ~50 calls, so the timed region cannot carry them all.)
+    survey = max(1, min(2, args.warmup))
+    for _ in range(max(0, args.warmup - survey)):
+        arr.train_step()
+    torch.cuda.synchronize()
+    tracer.enabled = True
+    for _ in range(survey):
+        arr.train_step()
+    tot = tracer.summary()
+    per_kernel = {k: dict(launches_per_step=v[0] // survey, ms_per_step=v[1] / survey,
+                          GBps=(v[2] / 1e9) / (v[1] / 1e3) if v[1] > 0 else None,
+                          TFLOPs=(v[3] / 1e12) / (v[1] / 1e3) if v[1] > 0 and v[3] > 0 else None)
+                  for k, v in sorted(tot.items(), key=lambda kv: -kv[1][1])}
+    dom = max(tot.items(), key=lambda kv: kv[1][1])[0]
+    # Timed regions: only the dominant entry's launches are bracketed, live, inside them
+    tracer.events = []
+    tracer.only = dom
+    secs = []
+    for _ in range(args.repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            arr.train_step()
+        torch.cuda.synchronize()
+        secs.append((time.perf_counter() - t0) / args.steps)
+    tracer.enabled = False
+    sec = float(np.mean(secs))
+    nsteps = args.steps * args.repeats
+    dv = tracer.summary()[dom]
+    samples = wl.samples
+    # HBM bytes per launch of that entry from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    # runs of this same command (profiles/<workload>_traffic.json); null when not collected
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"{name}_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(dom)
+    common = dict(kernel=dom, traffic=traffic, avg_launch_us=1e3 * dv[1] / dv[0],
+                  launches_per_step=dv[0] // nsteps, algorithmic_bytes_per_launch=dv[2] / dv[0],
+                  share_of_step=(dv[1] / nsteps) / (sec * 1e3))
+    if dv[3] > 0 and dv[3] / dv[2] > BF16_RIDGE and spec.dtype == "bf16":
+        achieved = (dv[3] / 1e12) / (dv[1] / 1e3)
+        roofline = dict(bound="mfma", achieved=achieved, peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=achieved / MFMA_PEAK_TFLOPS, algorithmic_flop_per_launch=dv[3] / dv[0], **common)
+    else:
+        achieved = (dv[2] / dv[0]) / 1e9 / ((dv[1] / dv[0]) / 1e3)
+        roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=achieved / HBM_PEAK_GBS, **common)
+    del arr
+    torch.cuda.empty_cache()
+
+    serial = None
+    if not args.skip_serial:
+        arrays.hb = binding
+        nser = max(3, args.steps // 4)
+        rep = np.zeros(args.repeats)
+        for b in range(spec.B):          # one model resident at a time: B models, one after another
+            s1, i1 = wl.one_model(b)
+            mdl = wl.cls(s1, i1)
+            rep += np.array([time_steps(mdl, torch, nser, 2 if r == 0 else 0) for r in range(args.repeats)])
+            del mdl
+        ssec = float(rep.mean())
+        serial = dict(value=samples / ssec, unit="samples/s", ms_per_step_all_models=ssec * 1e3,
+                      ms_per_step_all_models_stats=_stats(rep * 1e3), fused_speedup=ssec / sec,
+                      steps_per_model=nser, repeats=args.repeats)
+        torch.cuda.empty_cache()
+
+    cpu = None if args.skip_cpu else wl.cpu_baseline()
+    return {
+        "value": samples / sec, "unit": "samples/s", "ms_per_step": sec * 1e3,
+        "repeats": args.repeats, "value_stats": _stats([samples / t for t in secs]),
+        "ms_per_step_stats": _stats([t * 1e3 for t in secs]),
+        "dtype": spec.dtype, "data": "synthetic", "config": wl.config,
+        "roofline": roofline, "serial_b1": serial, "cpu_baseline": cpu, "kernels": per_kernel,
+        "kernels_note": f"per-entry HIP-event times from the last {survey} warm-up step(s); the roofline entry is timed inside the timed regions",
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c1t", "c2", "c3", "c4", "t0"])
+    ap.add_argument("--repeats", type=int, default=3, help="timed regions of --steps steps each; mean / min / max are reported")
+    ap.add_argument("--workload", default="all", choices=["all", "c0", "c1", "c1t", "c2", "c3", "c4", "t0"],
+                    help="all (default): config 1 as the headline line plus a `workloads` block with configs 0, 2, 3, 4 "
+                         "and the operator table; a name: that workload alone")
     ap.add_argument("--unfused", type=int, default=0,
                     help="config 1 only: run the first K per-point layers (and their share of Adam) model by model "
                          "(partial fusion); the headline line is K = 0")
     ap.add_argument("--skip-serial", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--skip-ops", action="store_true", help="leave the operator table out of the default run")
     ap.add_argument("--ops-report", default=None,
-                    help="also time the GEMM / conv2d entry points at config 4 / config 3 shapes and write JSON here")
+                    help="also write the operator table (GEMMs at config 4 shapes, conv2d at config 3 shapes) as JSON here")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -563,8 +662,6 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
-    wl = Workload(args.workload)
-    spec, inp = wl.spec, wl.inp
 
     if args.copy_ref:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda")      # 1 GiB read + 1 GiB written
@@ -573,87 +670,34 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    tracer = Tracer(binding, torch)
-    arrays.hb = tracer
-    arr = wl.cls(spec, inp, unfused_layers=tuple(range(args.unfused))) if (args.unfused and args.workload == "c1") else wl.cls(spec, inp)
-    if args.unfused and args.workload == "c1":
-        wl.config["unfused_per_point_layers"] = args.unfused
-    # Warm-up.  Its last steps bracket EVERY traced entry point with HIP events: the per-kernel table,
-    # and which entry has the largest share of a step.  (Two events per call cost host time, about
-    # as much as a whole step of this workload for ~50 calls, so the timed region cannot carry them all.)
-    survey = max(1, min(2, args.warmup))
-    for _ in range(max(0, args.warmup - survey)):
-        arr.train_step()
-    torch.cuda.synchronize()
-    tracer.enabled = True
-    for _ in range(survey):
-        arr.train_step()
-    tot = tracer.summary()
-    per_kernel = {k: dict(launches_per_step=v[0] // survey, ms_per_step=v[1] / survey,
-                          GBps=(v[2] / 1e9) / (v[1] / 1e3) if v[1] > 0 else None,
-                          TFLOPs=(v[3] / 1e12) / (v[1] / 1e3) if v[1] > 0 and v[3] > 0 else None)
-                  for k, v in sorted(tot.items(), key=lambda kv: -kv[1][1])}
-    dom = max(tot.items(), key=lambda kv: kv[1][1])[0]
-    # Timed region: only the dominant entry's launches are bracketed, live, inside it
-    tracer.events = []
-    tracer.only = dom
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        arr.train_step()
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / args.steps
-    tracer.enabled = False
-    dv = tracer.summary()[dom]
-    samples = wl.samples
-    value = samples / sec
-    # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    # runs of this same command (profiles/<workload>_*_hbm_traffic.md); null when not collected
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"{args.workload}_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(dom)
-    common = dict(kernel=dom, traffic=traffic, avg_launch_us=1e3 * dv[1] / dv[0],
-                  launches_per_step=dv[0] // args.steps, algorithmic_bytes_per_launch=dv[2] / dv[0],
-                  share_of_step=(dv[1] / args.steps) / (sec * 1e3))
-    if dv[3] > 0 and dv[3] / dv[2] > BF16_RIDGE and spec.dtype == "bf16":
-        achieved = (dv[3] / 1e12) / (dv[1] / 1e3)
-        roofline = dict(bound="mfma", achieved=achieved, peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=achieved / MFMA_PEAK_TFLOPS, algorithmic_flop_per_launch=dv[3] / dv[0], **common)
-    else:
-        achieved = (dv[2] / dv[0]) / 1e9 / ((dv[1] / dv[0]) / 1e3)
-        roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=achieved / HBM_PEAK_GBS, **common)
-
-    serial = None
-    if not args.skip_serial:
-        arrays.hb = binding
-        per_model = []
-        nser = max(3, args.steps // 4)
-        for b in range(spec.B):          # one model resident at a time: B models, one after another
-            s1, i1 = wl.one_model(b)
-            mdl = wl.cls(s1, i1)
-            per_model.append(time_steps(mdl, torch, nser, 2))
-            del mdl
-        ssec = sum(per_model)
-        serial = dict(value=samples / ssec, unit="samples/s", ms_per_step_all_models=ssec * 1e3,
-                      fused_speedup=ssec / sec)
-
-    cpu = None
-    if not args.skip_cpu:
-        cpu = wl.cpu_baseline()
-
+    head_name = "c1" if args.workload == "all" else args.workload
+    t_start = time.perf_counter()
+    head = run_workload(head_name, args, torch, arrays, binding)
     out = {
         "metric": "fused train samples/sec summed over B models",
-        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": spec.dtype, "data": "synthetic", "config": wl.config,
-        "roofline": roofline, "serial_b1": serial, "cpu_baseline": cpu, "kernels": per_kernel,
-        "kernels_note": f"per-entry HIP-event times from the last {survey} warm-up step(s); the roofline entry is timed inside the timed region",
+        "value": head["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
     }
-    if args.ops_report:
-        with open(args.ops_report, "w") as f:
-            json.dump(ops_report(torch, binding), f, indent=1)
+    out.update({k: v for k, v in head.items() if k not in out})
+    if args.workload == "all":
+        # the other BASELINE configurations, same legs each: the small fp32 case, the segmentation
+        # array, the GAN array and the MLP-block array (one JSON line carries all five)
+        out["workloads"] = {}
+        for name in ("c0", "c2", "c3", "c4"):
+            print(f"bench.py: {name} ... ({time.perf_counter() - t_start:.0f} s so far)", file=sys.stderr, flush=True)
+            w = run_workload(name, args, torch, arrays, binding)
+            w.pop("kernels_note", None)
+            out["workloads"][name] = w
+    if args.ops_report or (args.workload == "all" and not args.skip_ops):
+        print(f"bench.py: operator table ... ({time.perf_counter() - t_start:.0f} s so far)", file=sys.stderr, flush=True)
+        ops = ops_report(torch, binding)
+        if args.ops_report:
+            with open(args.ops_report, "w") as f:
+                json.dump(ops, f, indent=1)
+        if args.workload == "all":
+            out["operators"] = ops
+            out["operators_note"] = ("entry points timed alone with HIP events (30 warm-up + 100 launches): fused Linear at "
+                                     "config 4 shapes, grouped conv2d at config 3 shapes, against the dense bf16 MFMA peak")
     print(json.dumps(out))
 
 

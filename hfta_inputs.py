@@ -288,10 +288,9 @@ def seg_thin(B: int, Nb: int, L: int, dtype: str, div: int = 8) -> PointNetSegSp
 
 
 def pointnet_seg_param_shapes(spec: PointNetSegSpec) -> List[Tuple[str, Tuple[int, ...]]]:
-    """Per-model parameters in arena order.  The first head layer's ``[head[1], head[0]]`` weight is
-    kept as two blocks: ``head0.w`` ``[head[1], c_point]`` applied to the per-point features
-    (a k=1 convolution) and ``head0.wg`` ``[c_global, head[1]]`` applied once per sample to the tiled
-    part (a Linear); together they are the 4944-wide convolution of the layer list."""
+    """Per-model parameters of the layer list.  The first head layer has ONE ``[head[1], head[0]]``
+    weight over the whole concatenation (per-point features, then the tiled global feature, then the
+    tiled one-hot); how an implementation stores it is its own business."""
     out: List[Tuple[str, Tuple[int, ...]]] = []
     for i in range(len(spec.conv) - 1):
         ci, co = spec.conv[i], spec.conv[i + 1]
@@ -299,10 +298,7 @@ def pointnet_seg_param_shapes(spec: PointNetSegSpec) -> List[Tuple[str, Tuple[in
     nh = len(spec.head) - 1
     for i in range(nh):
         ci, co = spec.head[i], spec.head[i + 1]
-        if i == 0:
-            out += [("head0.w", (co, spec.c_point)), ("head0.wg", (spec.c_global, co)), ("head0.b", (co,))]
-        else:
-            out += [(f"head{i}.w", (co, ci)), (f"head{i}.b", (co,))]
+        out += [(f"head{i}.w", (co, ci)), (f"head{i}.b", (co,))]
         if i < nh - 1:
             out += [(f"head{i}.bn.g", (co,)), (f"head{i}.bn.b", (co,))]
     return out
@@ -327,12 +323,12 @@ def pointnet_seg_inputs(spec: PointNetSegSpec, seed: Optional[int] = None) -> Di
         p = {}
         for name, shape in shapes:
             layer = name.split(".")[0]
-            fan_in = spec.head[0] if layer == "head0" else dict(shapes)[layer + ".w"][1]
+            fan_in = dict(shapes)[layer + ".w"][1]
             if name.endswith(".bn.g"):
                 p[name] = np.ones(shape, np.float32)
             elif name.endswith(".bn.b"):
                 p[name] = np.zeros(shape, np.float32)
-            elif name.endswith(".w") or name.endswith(".wg"):
+            elif name.endswith(".w"):
                 p[name] = uniform_fan_in(rng, shape, fan_in, 6.0).astype(np.float32)
             else:
                 p[name] = uniform_fan_in(rng, shape, fan_in, 1.0).astype(np.float32)

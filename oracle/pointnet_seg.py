@@ -15,11 +15,14 @@ k=1 convolutions (BatchNorm + ReLU on all but the last), whose output is a score
 per part class and point; softmax cross-entropy with mean reduction over all the
 model's points; Adam.
 
-The first head convolution acts on a concatenation whose tiled part is constant
-along the points: W [per-point | tiled] = W_p (per-point features) + (tiled
-vector W_g) broadcast over the points; the parameters are kept as those two
-blocks.  Storage rounding as in oracle/pointnet.py: every tensor kept in memory
-between two operators is rounded once to the storage dtype.
+The concatenation is written out: the head's input is one stored
+[Nb, c_point + c_global, L] tensor (np.concatenate of the feature maps and the
+two tiled vectors), its first layer ONE k=1 convolution with ONE
+[head[1], c_point + c_global] weight and one store, and the backward is that
+convolution's adjoint followed by the adjoints of concatenate and tile (slice;
+sum over the points).  How an implementation avoids forming the concatenation
+is not the oracle's business.  Storage rounding as in oracle/pointnet.py: every
+tensor kept in memory between two operators is rounded once to the storage dtype.
 """
 from __future__ import annotations
 
@@ -60,17 +63,14 @@ def forward_backward(spec, theta, points, labels, onehot, running=None, bn_eps=1
         a = S(ops.act_fwd(y, ops.ACT_RELU))
         feats.append(a)
     glob, idx = ops.maxpool_points_fwd(a)                      # [Nb, C], exact on stored values
-    L = a.shape[2]
-    cat_pt = np.concatenate(feats, axis=1)                      # [Nb, c_point, L]
-    tiled = np.concatenate([glob, S(onehot)], axis=1)           # [Nb, c_global]
+    Nb, L = a.shape[0], a.shape[2]
+    tile = lambda v: np.broadcast_to(np.asarray(v, np.float64)[:, :, None], v.shape + (L,))
+    cat = np.concatenate(feats + [tile(glob), tile(S(onehot))], axis=1)   # [Nb, c_point + c_global, L]
     # ---- head
-    h = cat_pt
+    h = cat
     for i in range(nh):
         k = f"head{i}"
         z = S(ops.conv1x1_fwd(h, lp[k + ".w"], lp[k + ".b"]))
-        if i == 0:
-            hg = S(ops.linear_fwd(tiled, lp["head0.wg"], None))  # [Nb, Co], once per sample
-            z = S(z + hg[:, :, None])
         if i == nh - 1:
             saved[k] = (h,)
             h = z
@@ -79,7 +79,6 @@ def forward_backward(spec, theta, points, labels, onehot, running=None, bn_eps=1
         saved[k] = (h, z, y, mean, invstd)
         h = S(ops.act_fwd(y, ops.ACT_RELU))
     logits = h                                                  # [Nb, n_parts, L]
-    Nb = logits.shape[0]
     flat = logits.transpose(0, 2, 1).reshape(Nb * L, -1)        # one row per point
     loss, dflat = ops.softmax_xent(flat, np.asarray(labels).reshape(-1))
     d = S(dflat.reshape(Nb, L, -1).transpose(0, 2, 1))
@@ -96,13 +95,10 @@ def forward_backward(spec, theta, points, labels, onehot, running=None, bn_eps=1
         hin = saved[k][0]
         dx, dw, db = ops.conv1x1_bwd(hin, lp[k + ".w"], d)
         grads[k + ".w"], grads[k + ".b"] = dw, db
-        if i == 0:
-            dhg = S(d.sum(axis=2))                               # the tiled part sees the sum over the points
-            dt_, dwg, _ = ops.linear_bwd(tiled, lp["head0.wg"], dhg)
-            grads["head0.wg"] = dwg
-            dglob = S(dt_)[:, :spec.conv[-1]]
         d = S(dx)
-    dcat = d                                                    # [Nb, c_point, L]
+    c_point, c4 = sum(spec.conv[1:]), spec.conv[-1]
+    dcat = d[:, :c_point]                                       # adjoint of concatenate: slices of the stored gradient
+    dglob = S(d[:, c_point:c_point + c4].sum(axis=2))           # adjoint of tile: sum over the points
     # ---- backward: per-point MLP; every feature map also receives its slice of the concatenation's gradient
     off = np.cumsum([0] + list(spec.conv[1:]))
     d = None

@@ -607,6 +607,7 @@ class FusedDcgan:
     def __init__(self, spec, inp: dict, device: str = "cuda"):
         import hfta_inputs as hi
         self.spec = spec
+        self.probe = None          # tests: called after every library call with the tensors it read and wrote
         self.B, self.Nb = spec.B, spec.Nb
         self.dt, self.tdt = _DT[spec.dtype], _TDT[spec.dtype]
         self.dev = torch.device(device)
@@ -661,6 +662,10 @@ class FusedDcgan:
         # large enough for the column-buffer lowering of every layer (its sample-folded GEMMs)
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
 
+    def _P(self, op, **kw):
+        if self.probe is not None:
+            self.probe(op, **kw)
+
     # ------------------------------------------------------------------ generator
     def g_forward(self):
         B, Nb, dt, s = self.B, self.Nb, self.dt, self.spec
@@ -672,14 +677,20 @@ class FusedDcgan:
             # ConvTranspose2d forward = the data-gradient form of the grouped convolution
             hb.conv2d_grouped_bwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, None, self.G.w(k + ".w"), x,
                                   self.g_pre[i], None, None, self.ws)
+            self._P("convT2d_fwd", layer=k, x=x, w=self.G.w(k + ".w"), y=self.g_pre[i], geo=(ci, co, st, p))
             if i < n - 1:
                 cs = _cs(B, co, ho * ho)
                 hb.bn_fwd(B, Nb, co, ho * ho, dt, self.g_pre[i], cs, self.G.master(k + ".bn.g"),
                           self.G.master(k + ".bn.b"), self.BN_EPS, self.BN_MOMENTUM, self.running[k + ".bn.rm"],
                           self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
                           self.g_act[i], cs, hb.ACT_RELU)
+                self._P("bn_fwd", layer=k, x=self.g_pre[i], g=self.G.master(k + ".bn.g"), b=self.G.master(k + ".bn.b"),
+                        y=self.g_act[i], mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
+                        act=hb.ACT_RELU)
             else:
+                pre = self.g_pre[i].clone() if self.probe is not None else None
                 hb.bias_act_nchw(Nb, B * co, ho * ho, dt, self.g_pre[i], None, hb.ACT_TANH)
+                self._P("act_fwd", layer=k, x=pre, y=self.g_pre[i], act=hb.ACT_TANH)
             x = self.g_act[i]
         return self.fake
 
@@ -695,20 +706,27 @@ class FusedDcgan:
             dpre = self._other(d)[:cnt]
             if i == n - 1:
                 hb.act_bwd(cnt, dt, self.fake, d, dpre, hb.ACT_TANH, 0.0, 1)
+                self._P("act_bwd_from_output", layer=k, y=self.fake, dy=d[:cnt], dx=dpre, act=hb.ACT_TANH)
             else:
                 cs = _cs(B, co, ho * ho)
                 hb.bn_bwd(B, Nb, co, ho * ho, dt, self.g_pre[i], cs, d, cs, self.G.master(k + ".bn.g"),
                           self.G.master(k + ".bn.b"), self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
                           dpre, cs, self.G.g(k + ".bn.g"), self.G.g(k + ".bn.b"), hb.ACT_RELU, 0.0)
+                self._P("bn_bwd", layer=k, x=self.g_pre[i], dy=d[:cnt], g=self.G.master(k + ".bn.g"),
+                        b=self.G.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
+                        dx=dpre, dg=self.G.g(k + ".bn.g"), db=self.G.g(k + ".bn.b"), act=hb.ACT_RELU)
             xin = self.z if i == 0 else self.g_act[i - 1]
             # ConvTranspose2d weight gradient = the convolution's with input and output gradient exchanged
             hb.conv2d_grouped_bwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, dpre, None, xin, None,
                                   self.G.g(k + ".w"), None, self.ws)
+            self._P("convT2d_dw", layer=k, x=xin, w=self.G.w(k + ".w"), dy=dpre, dw=self.G.g(k + ".w"), geo=(ci, co, st, p),
+                    hw=(hin, ho))
             if i > 0:
                 dx = self._other(dpre)[:Nb * B * ci * hin * hin]      # the incoming gradient's buffer: it is dead
                 # ConvTranspose2d data gradient = the convolution's forward
                 hb.conv2d_grouped_fwd(B, Nb, co, ci, ho, ho, 4, 4, st, p, dt, dpre, self.G.w(k + ".w"), None, dx,
                                       workspace=self.ws)
+                self._P("convT2d_dx", layer=k, x=xin, w=self.G.w(k + ".w"), dy=dpre, dx=dx, geo=(ci, co, st, p), hw=(hin, ho))
                 d = dx
 
     def _other(self, t):
@@ -726,15 +744,20 @@ class FusedDcgan:
             if i == 0:
                 hb.conv2d_grouped_fwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, x, self.D.w(k + ".w"), None,
                                       self.d_pre[i], hb.ACT_LEAKY, self.SLOPE, workspace=self.ws)
+                self._P("conv2d_fwd", layer=k, x=x, w=self.D.w(k + ".w"), y=self.d_pre[i], geo=(ci, co, st, p), act=hb.ACT_LEAKY)
             else:
                 hb.conv2d_grouped_fwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, x, self.D.w(k + ".w"), None,
                                       self.d_pre[i], workspace=self.ws)
+                self._P("conv2d_fwd", layer=k, x=x, w=self.D.w(k + ".w"), y=self.d_pre[i], geo=(ci, co, st, p), act=hb.ACT_NONE)
                 if i < n - 1:
                     cs = _cs(B, co, ho * ho)
                     hb.bn_fwd(B, Nb, co, ho * ho, dt, self.d_pre[i], cs, self.D.master(k + ".bn.g"),
                               self.D.master(k + ".bn.b"), self.BN_EPS, self.BN_MOMENTUM, self.running[k + ".bn.rm"],
                               self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
                               self.d_act[i], cs, hb.ACT_LEAKY, self.SLOPE)
+                    self._P("bn_fwd", layer=k, x=self.d_pre[i], g=self.D.master(k + ".bn.g"), b=self.D.master(k + ".bn.b"),
+                            y=self.d_act[i], mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
+                            act=hb.ACT_LEAKY)
             x = self.d_act[i]
         return self.logits
 
@@ -754,6 +777,7 @@ class FusedDcgan:
                 dpre = self._other(d)[:cnt]
                 if i == 0:
                     hb.act_bwd(cnt, dt, self.d_act[0], d, dpre, hb.ACT_LEAKY, self.SLOPE, 1)
+                    self._P("act_bwd_from_output", layer=k, y=self.d_act[0], dy=d[:cnt], dx=dpre, act=hb.ACT_LEAKY)
                 else:
                     cs = _cs(B, co, ho * ho)
                     # without weight gradients the BatchNorm parameter gradients go to the spare buffer
@@ -761,20 +785,27 @@ class FusedDcgan:
                     hb.bn_bwd(B, Nb, co, ho * ho, dt, self.d_pre[i], cs, d, cs, self.D.master(k + ".bn.g"),
                               self.D.master(k + ".bn.b"), self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"],
                               dpre, cs, tgt(k + ".bn.g"), tgt(k + ".bn.b"), hb.ACT_LEAKY, self.SLOPE)
+                    self._P("bn_bwd", layer=k, x=self.d_pre[i], dy=d[:cnt], g=self.D.master(k + ".bn.g"),
+                            b=self.D.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"],
+                            dx=dpre, dg=tgt(k + ".bn.g"), db=tgt(k + ".bn.b"), act=hb.ACT_LEAKY)
             xin = self._d_in if i == 0 else self.d_act[i - 1]
             need_dx = i > 0 or want_dx
             if want_dw:
                 hb.conv2d_grouped_bwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, xin, None, dpre, None,
                                       grad_of(k + ".w"), None, self.ws)
+                self._P("conv2d_dw", layer=k, x=xin, w=self.D.w(k + ".w"), dy=dpre, dw=grad_of(k + ".w"), geo=(ci, co, st, p),
+                        hw=(hin, ho))
             if need_dx:
                 dx = self._other(dpre)[:Nb * B * ci * hin * hin]
                 hb.conv2d_grouped_bwd(B, Nb, ci, co, hin, hin, 4, 4, st, p, dt, None, self.D.w(k + ".w"), dpre, dx,
                                       None, None, self.ws)
+                self._P("conv2d_dx", layer=k, x=xin, w=self.D.w(k + ".w"), dy=dpre, dx=dx, geo=(ci, co, st, p), hw=(hin, ho))
                 d = dx
         return d
 
     def _bce(self, targets, loss):
         hb.bce_logits_strided(self.B, self.Nb, self.dt, self.logits, targets, loss, self.dlogits, 1, self.B)
+        self._P("bce", logits=self.logits, targets=targets, loss=loss, d=self.dlogits)
 
     # ------------------------------------------------------------------ one iteration
     def d_step(self):
@@ -785,7 +816,9 @@ class FusedDcgan:
         self.d_forward(self.fake)
         self._bce(self.zeros, self.loss_d_fake)
         self.d_backward(self.D.g2)
+        g1 = self.D.grad.clone() if self.probe is not None else None
         hb.add(self.D.grad.numel(), hb.F32, self.D.grad, self.D.grad2, self.D.grad)
+        self._P("grad_add", a=g1, b=self.D.grad2, y=self.D.grad)
 
     def g_step_backward(self):
         """Generator loss BCE(D(fake), 1) through the current discriminator, back to G's parameters."""
@@ -825,7 +858,18 @@ class FusedPointNetSeg(ParamArena):
         self.dev = torch.device(device)
         B, Nb, L = self.B, self.Nb, self.L
         import hfta_inputs as hi
-        self._init_arena(hi.pointnet_seg_param_shapes(spec), B, inp, spec.dtype, self.dev)
+        # The layer list's first head weight [head[1], c_point + c_global] is stored as two arena
+        # tensors: its per-point columns as a k=1 convolution weight ``head0.w`` [co, c_point], and its
+        # tiled columns transposed, ``head0.wg`` [c_global, co], the weight of a Linear applied once per
+        # sample (a convolution over channels that are constant along the points).
+        self.param_shapes = hi.pointnet_seg_param_shapes(spec)
+        shapes = []
+        for name, shp in self.param_shapes:
+            if name == "head0.w":
+                shapes += [("head0.w", (shp[0], spec.c_point)), ("head0.wg", (spec.c_global, shp[0]))]
+            else:
+                shapes.append((name, shp))
+        self._init_arena(shapes, B, {**inp, "params": [self._split_head0(p) for p in inp["params"]]}, spec.dtype, self.dev)
         f32 = dict(dtype=torch.float32, device=self.dev)
         act = dict(dtype=self.tdt, device=self.dev)
         self.running: Dict[str, torch.Tensor] = {}
@@ -869,6 +913,23 @@ class FusedPointNetSeg(ParamArena):
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         self.points = torch.from_numpy(inp["points"]).to(self.tdt).to(self.dev)
         self.labels = torch.from_numpy(inp["labels"]).to(self.dev)
+
+    def _split_head0(self, p: dict) -> dict:
+        """Per-model parameters of the layer list -> the arena's tensors (a re-layout, no arithmetic)."""
+        q = dict(p)
+        w = np.asarray(p["head0.w"], np.float32)
+        q["head0.w"] = np.ascontiguousarray(w[:, :self.spec.c_point])
+        q["head0.wg"] = np.ascontiguousarray(w[:, self.spec.c_point:].T)
+        return q
+
+    def load_params(self, params) -> None:
+        super().load_params([self._split_head0(p) for p in params])
+
+    def param_host(self, buf: torch.Tensor, name: str, b: int) -> np.ndarray:
+        """Parameter ``name`` of the layer list for model b (the first head weight re-assembled)."""
+        if name == "head0.w":
+            return np.concatenate([super().param_host(buf, "head0.w", b), super().param_host(buf, "head0.wg", b).T], axis=1)
+        return super().param_host(buf, name, b)
 
     def _slice(self, buf, i):
         """Channel slice i of a concatenation buffer: (tensor whose data pointer is the slice's first

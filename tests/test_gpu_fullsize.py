@@ -296,61 +296,101 @@ def test_c4_fused_reductions_full_size():
     rel_ok(f64(dxs), dX.double().sum(dim=1).cpu().numpy(), 2e-4, "column sums of the stored dX")
 
 
-@pytest.mark.parametrize("Ci,Co,H", [(64, 128, 32), (3, 64, 64)])
-def test_c3_conv2d_full_size_sampled(Ci, Co, H):
-    """Config 3's discriminator layers: B=10 models, 64 images per model, 4x4 stride 2 pad 1, bf16."""
+def _gen(seed):
+    return torch.Generator(device="cuda").manual_seed(seed)
+
+
+def _host_slices(T, Nb, B, C, b, imgs=None, chans=None):
+    """float64 [n, C', H, W] slice of model b (and of a sample / channel subset) of an [Nb, B*C, H, W] tensor."""
+    v = T.view(Nb, B, C, T.shape[2], T.shape[3])[:, b]
+    if imgs is not None:
+        v = v[imgs]
+    if chans is not None:
+        v = v[:, chans]
+    return f64(v)
+
+
+@pytest.mark.parametrize("path", ["implicit", "lowered"])
+@pytest.mark.parametrize("Ci,Co,H,s,p", hi.DCGAN_D_LAYERS)
+def test_c3_conv2d_full_size(Ci, Co, H, s, p, path):
+    """Config 3's discriminator layers at full size (B=10 models, 64 images per model, 4x4 kernels, bf16),
+    on both convolution paths (implicit GEMM without a workspace; column-buffer lowering with one).
+    References are the oracle's conv2d_fwd / conv2d_bwd on gathered slices of the tensors the GPU read:
+    output and data gradient of four sampled images of two sampled models in full, the weight gradient
+    (a reduction over all 64 images) for eight sampled output channels of those models in full."""
     from paper_2102_02344_amd import binding as hb
-    B, Nb, k, s, p = 10, 64, 4, 2, 1
-    Ho = H // 2
-    g = torch.Generator(device="cuda").manual_seed(30 + Ci)
+    B, Nb, k = 10, 64, 4
+    Ho = (H + 2 * p - k) // s + 1
+    print(f"conv2d {Ci}->{Co} {H}x{H} s{s} p{p} {path}", flush=True)
+    g = _gen(300 + Ci)
     X = (torch.rand(Nb, B * Ci, H, H, device="cuda", generator=g) * 2 - 1).to(bf)
     W = (torch.randn(B * Co, Ci, k, k, device="cuda", generator=g) * 0.02).to(bf)
     dY = torch.randn(Nb, B * Co, Ho, Ho, device="cuda", generator=g).to(bf)
     Y = torch.empty_like(dY)
     dX = torch.empty_like(X)
     dW = torch.empty(B * Co, Ci, k, k, device="cuda")
-    ws = torch.empty(max(4, hb.conv2d_grouped_bwd_workspace_bytes(B, Nb, Ci, Co, H, H, k, k, s, p, DT["bf16"])),
-                     dtype=torch.uint8, device="cuda")
-    hb.conv2d_grouped_fwd(B, Nb, Ci, Co, H, H, k, k, s, p, DT["bf16"], X, W, None, Y)
-    hb.conv2d_grouped_bwd(B, Nb, Ci, Co, H, H, k, k, s, p, DT["bf16"], X, W, dY, dX, dW, None, ws)
+    geo = (B, Nb, Ci, Co, H, H, k, k, s, p, DT["bf16"])
+    if path == "lowered":
+        nws = max(hb.conv2d_grouped_bwd_workspace_bytes(*geo), hb.conv2d_grouped_fwd_workspace_bytes(*geo))
+    else:
+        nws = hb.conv2d_grouped_bwd_min_workspace_bytes(*geo)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+    hb.conv2d_grouped_fwd(*geo, X, W, None, Y, workspace=ws if path == "lowered" else None)
+    hb.conv2d_grouped_bwd(*geo, X, W, dY, dX, dW, None, ws)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(9)
-    Xp = torch.nn.functional.pad(X, (p, p, p, p))              # zero padding only; no arithmetic
-    S = 1500
-    n, b, o, y, x = (torch.from_numpy(rng.integers(0, m, S)).cuda() for m in (Nb, B, Co, Ho, Ho))
-    # forward: window of the padded input against the filter
-    ci = torch.arange(Ci, device="cuda")
-    ky = torch.arange(k, device="cuda")
-    win = Xp[n[:, None, None, None], (b * Ci)[:, None, None, None] + ci[None, :, None, None],
-             (s * y)[:, None, None, None] + ky[None, None, :, None], (s * x)[:, None, None, None] + ky[None, None, None, :]]
-    ref = (f64(win) * f64(W[b * Co + o])).sum(axis=(1, 2, 3))
-    rel_ok(f64(Y[n, b * Co + o, y, x]), ref, TOL["bf16"], "Y")
-    # weight gradient of sampled filter taps: full reduction over (n, y, x)
-    for b_, o_, c_, ky_, kx_ in zip(*(rng.integers(0, m, 16) for m in (B, Co, Ci, k, k))):
-        xs = f64(Xp[:, b_ * Ci + c_, ky_:ky_ + s * Ho:s, kx_:kx_ + s * Ho:s])
-        d = f64(dY[:, b_ * Co + o_])
-        ref = (xs * d).sum()
-        assert abs(float(dW[b_ * Co + o_, c_, ky_, kx_]) - ref) <= 2e-4 * max(abs(ref), 1e-2 * np.abs(xs * d).sum())
-    # data gradient at sampled input pixels: sum over (o, ky, kx) with (iy + p - ky) divisible by s
-    S2 = 400
-    n, b, c, iy, ix = (rng.integers(0, m, S2) for m in (Nb, B, Ci, H, H))
-    dYh, Wh = f64(dY[:8]), f64(W)          # restrict to the first 8 images to bound the host copy
-    n = n % 8
-    got = f64(dX[:8])[n, b * Ci + c, iy, ix]
-    ref = np.zeros(S2)
-    for q in range(S2):
-        acc = 0.0
-        for ky_ in range(k):
-            ty = iy[q] + p - ky_
-            if ty % s or not (0 <= ty // s < Ho):
-                continue
-            for kx_ in range(k):
-                tx = ix[q] + p - kx_
-                if tx % s or not (0 <= tx // s < Ho):
-                    continue
-                acc += (dYh[n[q], b[q] * Co:(b[q] + 1) * Co, ty // s, tx // s] * Wh[b[q] * Co:(b[q] + 1) * Co, c[q], ky_, kx_]).sum()
-        ref[q] = acc
-    rel_ok(got, ref, TOL["bf16"], "dX")
+    rng = np.random.default_rng(9 + Ci)
+    for b in rng.choice(B, 2, replace=False):
+        imgs = np.sort(rng.choice(Nb, 4, replace=False))
+        wb = f64(W[b * Co:(b + 1) * Co])
+        xb = _host_slices(X, Nb, B, Ci, b, imgs)
+        rel_ok(_host_slices(Y, Nb, B, Co, b, imgs), oops.conv2d_fwd(xb, wb, None, s, p), TOL["bf16"], "Y")
+        dx, _, _ = oops.conv2d_bwd(xb, wb, _host_slices(dY, Nb, B, Co, b, imgs), s, p)
+        rel_ok(_host_slices(dX, Nb, B, Ci, b, imgs), dx, TOL["bf16"], "dX")
+        oc = np.sort(rng.choice(Co, min(8, Co), replace=False))
+        _, dw, _ = oops.conv2d_bwd(_host_slices(X, Nb, B, Ci, b), wb[oc], _host_slices(dY, Nb, B, Co, b, chans=oc), s, p)
+        rel_ok(f64(dW[b * Co:(b + 1) * Co][oc]), dw, 2e-4, "dW")
+
+
+@pytest.mark.parametrize("path", ["implicit", "lowered"])
+@pytest.mark.parametrize("Cx,Cy,H,s,p", hi.DCGAN_G_LAYERS)
+def test_c3_convT2d_full_size(Cx, Cy, H, s, p, path):
+    """Config 3's generator layers (ConvTranspose2d, weights [B*Cx, Cy, 4, 4]) at full size, as the array
+    calls them: forward = the grouped convolution's data-gradient form, data gradient = its forward,
+    weight gradient = its weight gradient with input and output gradient exchanged.  References:
+    the oracle's convT2d_fwd / convT2d_bwd on gathered slices (four images of two models in full;
+    weight gradient of eight sampled input channels over all 64 images)."""
+    from paper_2102_02344_amd import binding as hb
+    B, Nb, k = 10, 64, 4
+    Ho = (H - 1) * s - 2 * p + k
+    print(f"convT2d {Cx}->{Cy} {H}x{H} s{s} p{p} {path}", flush=True)
+    g = _gen(400 + Cx)
+    X = torch.randn(Nb, B * Cx, H, H, device="cuda", generator=g).to(bf)
+    W = (torch.randn(B * Cx, Cy, k, k, device="cuda", generator=g) * 0.02).to(bf)
+    dY = torch.randn(Nb, B * Cy, Ho, Ho, device="cuda", generator=g).to(bf)
+    Y = torch.empty_like(dY)
+    dX = torch.empty_like(X)
+    dW = torch.empty(B * Cx, Cy, k, k, device="cuda")
+    geo = (B, Nb, Cy, Cx, Ho, Ho, k, k, s, p, DT["bf16"])          # the convolution this layer is the transpose of
+    if path == "lowered":
+        nws = max(hb.conv2d_grouped_bwd_workspace_bytes(*geo), hb.conv2d_grouped_fwd_workspace_bytes(*geo))
+    else:
+        nws = hb.conv2d_grouped_bwd_min_workspace_bytes(*geo)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+    hb.conv2d_grouped_bwd(*geo, None, W, X, Y, None, None, ws)                                   # ConvT forward
+    hb.conv2d_grouped_fwd(*geo, dY, W, None, dX, workspace=ws if path == "lowered" else None)    # ConvT data gradient
+    hb.conv2d_grouped_bwd(*geo, dY, None, X, None, dW, None, ws)                                 # ConvT weight gradient
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(19 + Cx)
+    for b in rng.choice(B, 2, replace=False):
+        imgs = np.sort(rng.choice(Nb, 4, replace=False))
+        wb = f64(W[b * Cx:(b + 1) * Cx])
+        xb = _host_slices(X, Nb, B, Cx, b, imgs)
+        rel_ok(_host_slices(Y, Nb, B, Cy, b, imgs), oops.convT2d_fwd(xb, wb, None, s, p), TOL["bf16"], "ConvT Y")
+        dx, _, _ = oops.convT2d_bwd(xb, wb, _host_slices(dY, Nb, B, Cy, b, imgs), s, p)
+        rel_ok(_host_slices(dX, Nb, B, Cx, b, imgs), dx, TOL["bf16"], "ConvT dX")
+        ic = np.sort(rng.choice(Cx, min(8, Cx), replace=False))
+        _, dw, _ = oops.convT2d_bwd(_host_slices(X, Nb, B, Cx, b, chans=ic), wb[ic], _host_slices(dY, Nb, B, Cy, b), s, p)
+        rel_ok(f64(dW[b * Cx:(b + 1) * Cx][ic]), dw, 2e-4, "ConvT dW")
 
 
 def test_c2_full_size_step_sampled():

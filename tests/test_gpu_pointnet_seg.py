@@ -143,7 +143,46 @@ def test_seg_every_call_in_place_and_chain(dtype):
     inp = hi.pointnet_seg_inputs(spec)
     arr = FusedPointNetSeg(spec, inp)
     seen = []
-    arr.forward_backward(seg_probe(spec, seen))
+    inner = seg_probe(spec, seen)
+    kept = {}
+    B, Nb, L, Cp, Cg, co = spec.B, spec.Nb, spec.L, spec.c_point, spec.c_global, spec.head[1]
+
+    def probe(op, **kw):
+        """The per-call checks, plus: the head's first layer as the device runs it (convolution over the
+        per-point block, stored; once-per-sample block, stored; their sum, stored) against the layer's
+        plain definition -- ONE k=1 convolution of the explicit concatenation with the [Co, c_point +
+        c_global] weight, one store -- on the bits the GPU consumed, at the per-operator tolerance."""
+        inner(op, **kw)
+        if op == "conv1x1_fwd" and kw.get("layer") == "head0":
+            kept.update(x=H(kw["x"]), w=H(kw["w"]).reshape(B, co, Cp), b=H(kw["b"]).reshape(B, co))
+        elif op == "linear_fwd" and kw.get("layer") == "head0.wg":
+            kept.update(t=H(kw["x"]), wg=H(kw["w"]).reshape(B, Cg, co))
+        elif op == "add_sample_bias":
+            y = H(kw["y"]).reshape(Nb, B, co, L)
+            for b in range(B):
+                tiled = np.broadcast_to(kept["t"][b][:, :, None], (Nb, Cg, L))
+                cat = np.concatenate([kept["x"].reshape(Nb, B, Cp, L)[:, b], tiled], axis=1)
+                w_full = np.concatenate([kept["w"][b], kept["wg"][b].T], axis=1)
+                check(y[:, b], oops.conv1x1_fwd(cat, w_full, kept["b"][b]), TOL[dtype], "head0 vs its one-convolution definition")
+        elif op == "sum_points":
+            kept.update(dy=H(kw["x"]).reshape(Nb, B, co, L))
+        elif op == "linear_bwd" and kw.get("layer") == "head0.wg":
+            # backward of the same layer: gradient of the tiled channels = the point-sum of the one
+            # convolution's data gradient; weight gradient = that convolution's, column blocks side by side
+            for b in range(B):
+                tiled = np.broadcast_to(kept["t"][b][:, :, None], (Nb, Cg, L))
+                cat = np.concatenate([kept["x"].reshape(Nb, B, Cp, L)[:, b], tiled], axis=1)
+                w_full = np.concatenate([kept["w"][b], kept["wg"][b].T], axis=1)
+                dx, dw, _ = oops.conv1x1_bwd(cat, w_full, kept["dy"][:, b])
+                check(H(kw["dx"])[b], dx[:, Cp:].sum(axis=2), TOL[dtype], "head0 tiled-part gradient vs definition")
+                dwg = H(kw["dw"]).reshape(B, Cg, co)[b]
+                # the device stores the point-sum of dy in the storage dtype before this product (half an
+                # ulp of each of the Nb summed terms); the definition adds all Nb*L terms in one accumulator
+                ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -24     # half an ulp, relative, at worst
+                extra = ulp * np.einsum("no,nc->oc", np.abs(kept["dy"][:, b].sum(axis=2)), np.abs(kept["t"][b]))
+                check(dwg.T, dw[:, Cp:], 1e-5 if dtype == "f32" else 2e-4, "head0 tiled-block weight gradient vs definition", extra)
+
+    arr.forward_backward(probe)
     nconv, nh = len(spec.conv) - 1, len(spec.head) - 1
     assert len(seen) == 2 * nconv + 1 + 1 + nh + 1 + (nh - 1) + 1 + (nh - 1) + nh + 2 + 1 + (nconv - 1) + 2 * nconv
     states = [oseg.init_state(inp["params"][b]) for b in range(spec.B)]
@@ -153,9 +192,10 @@ def test_seg_every_call_in_place_and_chain(dtype):
     for b in range(spec.B):
         assert abs(loss[b] - outs[b]["loss"]) <= tol * abs(outs[b]["loss"]), (b, loss[b], outs[b]["loss"])
     if dtype == "f32":
-        wmax = {b: max(np.abs(outs[b]["grads"][n]).max() for n, _ in arr.shapes if n.endswith(".w")) for b in range(spec.B)}
+        # parameters by the layer list's names (the first head weight is one [Co, c_point + c_global] matrix)
+        wmax = {b: max(np.abs(outs[b]["grads"][n]).max() for n, _ in arr.param_shapes if n.endswith(".w")) for b in range(spec.B)}
         for b in range(spec.B):
-            for name, _ in arr.shapes:
+            for name, _ in arr.param_shapes:
                 g = arr.param_host(arr.grad, name, b).astype(np.float64)
                 ref = outs[b]["grads"][name]
                 if name.endswith(".b") and ".bn." not in name and name != f"head{nh - 1}.b":
@@ -167,7 +207,7 @@ def test_seg_every_call_in_place_and_chain(dtype):
         torch.cuda.synchronize()
         for b in range(spec.B):
             lr = float(inp["lr"][b])
-            for name, _ in arr.shapes:
+            for name, _ in arr.param_shapes:
                 th = arr.param_host(arr.theta, name, b).astype(np.float64)
                 assert np.abs(th - states[b]["theta"][name]).max() <= 2.5 * lr, (name, b)
 
@@ -188,6 +228,6 @@ def test_seg_fused_equals_serial_B1_on_gpu():
     one.train_step()
     torch.cuda.synchronize()
     assert abs(float(arr.loss[1]) - float(one.loss[0])) <= 1e-6 * abs(float(one.loss[0]))
-    for name, _ in arr.shapes:
+    for name, _ in arr.param_shapes:
         a, o = arr.param_host(arr.theta, name, 1), one.param_host(one.theta, name, 0)
         assert np.abs(a - o).max() <= 1e-6 * max(np.abs(o).max(), 1e-3) + 2.5 * float(inp["lr"][1]) * 1e-3, name

@@ -1,7 +1,7 @@
 """Pins for the segmentation-style oracle step (no GPU needed): the same network written with
 torch's CPU float64 operators as ONE 4944-style convolution over an explicit concatenation
-(torch.cat + expand) and differentiated by autograd, which also pins the split of the first
-head weight into a per-point block and a once-per-sample block; Adam against torch.optim;
+(torch.cat + expand) and differentiated by autograd; the identity that lets an implementation
+split the first head weight into a per-point block and a once-per-sample block; Adam against torch.optim;
 independence of the models of an array."""
 import dataclasses
 
@@ -31,12 +31,10 @@ def torch_loss(spec, tp, points, labels, onehot):
     L = a.shape[2]
     g = a.max(dim=2).values
     cat = torch.cat(feats + [g[:, :, None].expand(-1, -1, L), T(onehot)[:, :, None].expand(-1, -1, L)], dim=1)
-    # the layer list's single first head convolution: [Co, c_point + c_global]
-    w0 = torch.cat([tp["head0.w"], tp["head0.wg"].t()], dim=1)
     nh = len(spec.head) - 1
     h = cat
     for i in range(nh):
-        w = w0 if i == 0 else tp[f"head{i}.w"]
+        w = tp[f"head{i}.w"]                 # head0.w: [Co, c_point + c_global], one convolution
         h = F.conv1d(h, w[:, :, None], tp[f"head{i}.b"])
         if i < nh - 1:
             h = F.relu(F.batch_norm(h, None, None, tp[f"head{i}.bn.g"], tp[f"head{i}.bn.b"], training=True, eps=1e-5))
@@ -99,4 +97,27 @@ def test_inputs_recipe():
     assert inp["points"].shape == (2, 6, 40) and inp["labels"].shape == (2, 2, 40) and inp["labels"].max() < 50
     assert np.all(np.linalg.norm(inp["points"][:, :3, :].astype(np.float64), axis=1) <= 1.0 + 1e-2)
     assert np.array_equal(inp["onehot"].sum(axis=2), np.ones((2, 2)))
-    assert [n for n, _ in hi.pointnet_seg_param_shapes(thin)][20:23] == ["head0.w", "head0.wg", "head0.b"]
+    shapes = dict(hi.pointnet_seg_param_shapes(thin))
+    assert shapes["head0.w"] == (thin.head[1], thin.c_point + thin.c_global) and "head0.wg" not in shapes
+
+
+def test_split_first_head_layer_identity():
+    """A k=1 convolution over [per-point maps | tiled vector] equals the convolution of the per-point
+    block plus the tiled block's product taken once per sample and broadcast along the points, and its
+    adjoint hands the tiled part the point-sum of the output gradient: the decomposition the device
+    uses, checked here on the oracle's own operators in float64."""
+    from oracle import ops
+    rng = np.random.default_rng(3)
+    Nb, Cp, Cg, Co, L = 3, 5, 4, 6, 7
+    xp, t = rng.standard_normal((Nb, Cp, L)), rng.standard_normal((Nb, Cg))
+    w, b, dy = rng.standard_normal((Co, Cp + Cg)), rng.standard_normal(Co), rng.standard_normal((Nb, Co, L))
+    cat = np.concatenate([xp, np.broadcast_to(t[:, :, None], (Nb, Cg, L))], axis=1)
+    y = ops.conv1x1_fwd(cat, w, b)
+    hg = ops.linear_fwd(t, w[:, Cp:].T.copy(), None)
+    np.testing.assert_allclose(ops.add_sample_bias(ops.conv1x1_fwd(xp, w[:, :Cp].copy(), b), hg), y, rtol=0, atol=1e-12)
+    dx, dw, _ = ops.conv1x1_bwd(cat, w, dy)
+    dxp, dwp, _ = ops.conv1x1_bwd(xp, w[:, :Cp].copy(), dy)
+    dt, dwg, _ = ops.linear_bwd(t, w[:, Cp:].T.copy(), ops.sum_points(dy))
+    np.testing.assert_allclose(dxp, dx[:, :Cp], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dt, dx[:, Cp:].sum(axis=2), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(np.concatenate([dwp, dwg.T], axis=1), dw, rtol=0, atol=1e-12)
