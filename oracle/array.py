@@ -131,6 +131,22 @@ def bn_fwd(B, x, gamma, beta, eps=1e-5, momentum=0.1, running_mean=None, running
     return y, mean, invstd, nrm, nrv
 
 
+def bn_eval_fwd(B, x, gamma, beta, running_mean, running_var, eps=1e-5, layout="conv"):
+    """Evaluation-mode BatchNorm of the array: model b's channels with model b's running estimates."""
+    if layout == "linear":
+        Bn, N, C = x.shape
+        xc = np.transpose(x, (1, 0, 2)).reshape(N, B * C, 1)
+        y = bn_eval_fwd(B, xc, np.reshape(gamma, -1), np.reshape(beta, -1), np.reshape(running_mean, -1),
+                        np.reshape(running_var, -1), eps, "conv")
+        return y.reshape(N, B, C).transpose(1, 0, 2)
+    C = x.shape[1] // B
+    y = np.empty(x.shape, F64)
+    for b in range(B):
+        s = slice(b * C, (b + 1) * C)
+        y[:, s] = ops.bn_eval_fwd(x[:, s], gamma[s], beta[s], running_mean[s], running_var[s], eps)
+    return y
+
+
 def bn_bwd(B, x, dy, gamma, mean, invstd, layout="conv"):
     if layout == "linear":
         Bn, N, C = x.shape

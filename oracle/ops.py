@@ -219,6 +219,15 @@ def bn_fwd(x, gamma, beta, eps: float = 1e-5, momentum: float = 0.1,
     return y, mu, invstd, nrm, nrv
 
 
+def bn_eval_fwd(x, gamma, beta, running_mean, running_var, eps: float = 1e-5):
+    """Evaluation mode (the fusion rules table keeps every argument of the single-model operator,
+    its training flag included): the running estimates take the place of the batch statistics,
+    y = gamma (x - running_mean) / sqrt(running_var + eps) + beta; nothing is updated.  x:[N,C,L]."""
+    x = _f64(x)
+    scale = _f64(gamma) / np.sqrt(_f64(running_var) + eps)
+    return (x - _f64(running_mean)[None, :, None]) * scale[None, :, None] + _f64(beta)[None, :, None]
+
+
 def bn_bwd(x, dy, gamma, mean, invstd):
     """dbeta = sum dy; dgamma = sum dy xhat;
     dx = gamma invstd (dy - dbeta/m - xhat dgamma/m).  Returns (dx, dgamma, dbeta)."""

@@ -16,11 +16,18 @@ mean reduction over the model's own batch; Adam.
 Storage rounding: every activation / activation-gradient tensor that the
 library keeps in memory between two operators is rounded once to the storage
 dtype (``ops.store``); statistics, parameter gradients and optimiser state are
-float32; arithmetic inside an operator is float64.  With ``fused_tail`` the last
-per-point layer, its BatchNorm, ReLU and the max over points are ONE operator
-(``ops.conv1x1_bn_maxpool_fwd`` / ``_bwd``), forward and backward: it keeps no
-[N, C, L] tensor, so nothing inside it is rounded; only its pooled output and
-its input gradient are stored.
+float32; arithmetic inside an operator is float64.  The model is written as the
+plain chain of single operators (convolution, BatchNorm, ReLU, max over points,
+...), each storing its result; an implementation that merges some of them has to
+stay within the tolerance of this chain.
+
+``idx_given``: after a chain of floating-point operators the argmax of the max
+over points can legitimately differ between two implementations at near-ties,
+and from there on the two would differentiate different functions.  A chain-level
+comparison therefore may hand the oracle the argmax another implementation took
+(after checking it against the oracle's own values): the pooled feature is then
+read at those positions and the backward scatters there.  Without it the oracle
+uses its own argmax (lowest index among equal stored values).
 """
 from __future__ import annotations
 
@@ -44,12 +51,12 @@ def init_state(params: Dict[str, np.ndarray]) -> Dict[str, Dict[str, np.ndarray]
     return st
 
 
-def chain_cfg(spec, conv=None, fc="spec", conv_base=0, fused_tail=False, prefix="", dropout_p=None, fc_bn=None):
+def chain_cfg(spec, conv=None, fc="spec", conv_base=0, prefix="", dropout_p=None, fc_bn=None):
     """Description of one chain: per-point layers conv[0] -> conv[-1] named
     ``{prefix}conv{conv_base + i}``, then (unless fc is None) the max over points and the fully
     connected layers ``{prefix}fc{i}``.  Defaults: the whole classification model of ``spec``."""
     return dict(conv=tuple(spec.conv if conv is None else conv), fc=(tuple(spec.fc) if fc == "spec" else fc),
-                conv_base=conv_base, fused_tail=fused_tail, prefix=prefix, dtype=spec.dtype,
+                conv_base=conv_base, prefix=prefix, dtype=spec.dtype,
                 fc_bn=spec.fc_bn if fc_bn is None else fc_bn,
                 dropout_p=spec.dropout_p if dropout_p is None else dropout_p)
 
@@ -60,35 +67,25 @@ def rounded_params(theta, dt):
                 np.asarray(v, np.float64)) for k, v in theta.items()}
 
 
-def chain_fwd(cfg, lp, a, drop_mask=None, running=None, new_running=None, bn_eps=1e-5, bn_momentum=0.1):
+def chain_fwd(cfg, lp, a, drop_mask=None, running=None, new_running=None, bn_eps=1e-5, bn_momentum=0.1,
+              idx_given=None):
     """Forward of one chain on a:[Nb,C,L].  Returns (out, ctx): out is the last activation
-    [Nb,C',L] (no head) or the last Linear's output [Nb,K]."""
+    [Nb,C',L] (no head) or the last Linear's output [Nb,K].  ctx["idx_own"] / ctx["pooled_own"] are the
+    oracle's own argmax and maximum; ctx["idx"] / ctx["pooled"] what the chain continued from."""
     dt, px, cb = cfg["dtype"], cfg["prefix"], cfg["conv_base"]
     S = lambda v: ops.store(v, dt)
     sdt = "f64" if dt == "f64" else "f32"       # saved statistics are float32 on the device
     nconv = len(cfg["conv"]) - 1
     head = cfg["fc"] is not None
     nfc = len(cfg["fc"]) - 1 if head else 0
-    fused_tail = cfg["fused_tail"] and head
     new_running = {} if new_running is None else new_running
     saved = {}
     a = np.asarray(a, np.float64)
-    pooled = idx = None
     for i in range(nconv):
         k = f"{px}conv{cb + i}"
         rm = rv = None
         if running is not None:
             rm, rv = running[k + ".bn.rm"], running[k + ".bn.rv"]
-        if fused_tail and i == nconv - 1:
-            pooled, idx, mean, invstd, nrm, nrv, _ = ops.conv1x1_bn_maxpool_fwd(
-                a, lp[k + ".w"], lp[k + ".b"], lp[k + ".bn.g"], lp[k + ".bn.b"], bn_eps,
-                bn_momentum, rm, rv, ops.ACT_RELU)
-            mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
-            if running is not None:
-                new_running[k + ".bn.rm"], new_running[k + ".bn.rv"] = nrm, nrv
-            saved[k] = (a, None, None, mean, invstd)
-            pooled = S(pooled)
-            break
         z = S(ops.conv1x1_fwd(a, lp[k + ".w"], lp[k + ".b"]))
         y, mean, invstd, nrm, nrv = ops.bn_fwd(z, lp[k + ".bn.g"], lp[k + ".bn.b"], bn_eps, bn_momentum, rm, rv)
         mean, invstd = ops.store(mean, sdt), ops.store(invstd, sdt)
@@ -96,11 +93,14 @@ def chain_fwd(cfg, lp, a, drop_mask=None, running=None, new_running=None, bn_eps
             new_running[k + ".bn.rm"], new_running[k + ".bn.rv"] = nrm, nrv
         saved[k] = (a, z, y, mean, invstd)
         a = S(ops.act_fwd(y, ops.ACT_RELU))
-    ctx = dict(saved=saved, Lp=a.shape[2], idx=idx, pooled=None)
+    ctx = dict(saved=saved, Lp=a.shape[2], idx=None, pooled=None, act=a)
     if not head:
         return a, ctx
-    if not fused_tail:
-        pooled, idx = ops.maxpool_points_fwd(a)
+    pooled, idx = ops.maxpool_points_fwd(a)
+    ctx["idx_own"], ctx["pooled_own"] = idx, pooled
+    if idx_given is not None:
+        idx = np.asarray(idx_given)
+        pooled = np.take_along_axis(a, idx[:, :, None].astype(np.int64), axis=2)[:, :, 0]
     ctx["idx"], ctx["pooled"] = idx, pooled
 
     h = pooled
@@ -144,7 +144,6 @@ def chain_bwd(cfg, lp, ctx, d, grads, drop_mask=None, want_dx=False):
     nconv = len(cfg["conv"]) - 1
     head = cfg["fc"] is not None
     nfc = len(cfg["fc"]) - 1 if head else 0
-    fused_tail = cfg["fused_tail"] and head
     saved, idx = ctx["saved"], ctx["idx"]
     for i in reversed(range(nfc)):
         k = f"{px}fc{i}"
@@ -166,19 +165,12 @@ def chain_bwd(cfg, lp, ctx, d, grads, drop_mask=None, want_dx=False):
         grads[k + ".w"], grads[k + ".b"] = dw, db
         d = S(dx)
 
-    if head and not fused_tail:
+    if head:
         d = ops.maxpool_points_bwd(d, idx, ctx["Lp"])      # exact scatter of stored values
     for i in reversed(range(nconv)):
         k = f"{px}conv{cb + i}"
         ain, z, y, mean, invstd = saved[k]
         need_dx = i > 0 or want_dx
-        if fused_tail and i == nconv - 1:
-            dx, dw, db, dg, dbt = ops.conv1x1_bn_maxpool_bwd(ain, lp[k + ".w"], lp[k + ".b"], lp[k + ".bn.g"],
-                                                             lp[k + ".bn.b"], mean, invstd, d, idx, ops.ACT_RELU)
-            grads[k + ".bn.g"], grads[k + ".bn.b"], grads[k + ".w"], grads[k + ".b"] = dg, dbt, dw, db
-            if need_dx:
-                d = S(dx)
-            continue
         dy = ops.act_bwd(y, d, ops.ACT_RELU)
         dz, dg, dbt = ops.bn_bwd(z, dy, lp[k + ".bn.g"], mean, invstd)
         grads[k + ".bn.g"], grads[k + ".bn.b"] = dg, dbt
@@ -191,28 +183,29 @@ def chain_bwd(cfg, lp, ctx, d, grads, drop_mask=None, want_dx=False):
 
 
 def forward_backward(spec, theta, points, labels, drop_mask=None, running=None,
-                     bn_eps=1e-5, bn_momentum=0.1, fused_tail=False):
+                     bn_eps=1e-5, bn_momentum=0.1, idx_given=None):
     """Forward + backward of one model.
 
-    points:[Nb,3,L], labels:[Nb], drop_mask:[Nb,F] or None.
-    Returns dict(loss, logits, grads{name->float64}, pool_idx, pooled, running{...}).
+    points:[Nb,3,L], labels:[Nb], drop_mask:[Nb,F] or None; idx_given:[Nb,C] or None (module docstring).
+    Returns dict(loss, logits, grads{name->float64}, pool_idx, pooled (the oracle's own argmax and
+    maximum), last_act (the stored [Nb,C,L] tensor the maximum is taken over), running{...}).
     """
-    cfg = chain_cfg(spec, fused_tail=fused_tail)
+    cfg = chain_cfg(spec)
     lp = rounded_params(theta, spec.dtype)
     new_running = {}
-    logits, ctx = chain_fwd(cfg, lp, points, drop_mask, running, new_running, bn_eps, bn_momentum)
+    logits, ctx = chain_fwd(cfg, lp, points, drop_mask, running, new_running, bn_eps, bn_momentum, idx_given)
     loss, dlogits = ops.softmax_xent(logits, labels)
     grads = {}
     chain_bwd(cfg, lp, ctx, ops.store(dlogits, spec.dtype), grads, drop_mask)
-    return dict(loss=loss, logits=logits, grads=grads, pool_idx=ctx["idx"], pooled=ctx["pooled"],
-                running=new_running)
+    return dict(loss=loss, logits=logits, grads=grads, pool_idx=ctx["idx_own"], pooled=ctx["pooled_own"],
+                last_act=ctx["act"], running=new_running)
 
 
-def train_step(spec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, fused_tail=False):
+def train_step(spec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, idx_given=None):
     """One fwd + bwd + optimiser step of one model; updates ``state`` in place.
     hp: dict(lr, beta1, beta2, eps, wd) scalars for Adam, dict(lr, rho, eps, wd) for Adadelta.
     Returns the forward/backward dict."""
-    out = forward_backward(spec, state["theta"], points, labels, drop_mask, state["running"], fused_tail=fused_tail)
+    out = forward_backward(spec, state["theta"], points, labels, drop_mask, state["running"], idx_given=idx_given)
     for k in state["theta"]:
         g = ops.store(out["grads"][k], "f32")
         if "rho" in hp:     # Adadelta: the two state buffers hold the running square average and the accumulated delta
@@ -229,12 +222,12 @@ def train_step(spec, state, points, labels, hp: Dict[str, float], t: int, drop_m
     return out
 
 
-def array_train_step(spec, states: List[dict], inp: dict, t: int, fused_tail=False):
-    """The array's reference: B separate unfused runs, one after another."""
+def array_train_step(spec, states: List[dict], inp: dict, t: int, idx_given=None):
+    """The array's reference: B separate unfused runs, one after another (idx_given: [B][Nb,C] or None)."""
     outs = []
     for b in range(spec.B):
         hp = {k: float(inp[k][b]) for k in ("lr", "beta1", "beta2", "eps", "wd", "rho") if k in inp}
         mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
         outs.append(train_step(spec, states[b], inp["points"][:, 3 * b:3 * b + 3, :],
-                               inp["labels"][b], hp, t, mask, fused_tail))
+                               inp["labels"][b], hp, t, mask, None if idx_given is None else idx_given[b]))
     return outs

@@ -28,15 +28,15 @@ from . import pointnet as pn
 init_state = pn.init_state
 
 
-def _tnet_cfg(tspec, k: int, fused_tail: bool):
+def _tnet_cfg(tspec, k: int):
     s = tspec.cls
     return pn.chain_cfg(s, conv=(k,) + tuple(tspec.tnet_conv), fc=(tspec.tnet_conv[-1],) + tuple(tspec.tnet_fc) + (k * k,),
-                        fused_tail=fused_tail, prefix=f"t{k}.", dropout_p=0.0, fc_bn=True)
+                        prefix=f"t{k}.", dropout_p=0.0, fc_bn=True)
 
 
-def _transform_fwd(tspec, k, lp, x, running, new_running, fused_tail, S, T_given=None):
-    cfg = _tnet_cfg(tspec, k, fused_tail)
-    o, ctx = pn.chain_fwd(cfg, lp, x, None, running, new_running)
+def _transform_fwd(tspec, k, lp, x, running, new_running, S, T_given=None, idx_given=None):
+    cfg = _tnet_cfg(tspec, k)
+    o, ctx = pn.chain_fwd(cfg, lp, x, None, running, new_running, idx_given=idx_given)
     T_own = S(o + np.eye(k).reshape(1, k * k)).reshape(-1, k, k)
     T = T_own if T_given is None else np.asarray(T_given, np.float64).reshape(-1, k, k)
     return S(ops.point_transform_fwd(x, T)), (cfg, ctx, T, x, T_own)
@@ -51,14 +51,19 @@ def _transform_bwd(lp, saved, dy, grads, S, want_dx):
     return S(S(dx_direct) + dx_net) if want_dx else None
 
 
-def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None, fused_tail=True, T_given=None):
-    """Forward + backward of one model.  Returns dict(loss, logits, grads, running, T3, T64).
+def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None, T_given=None, idx_given=None):
+    """Forward + backward of one model.  Returns dict(loss, logits, grads, running, T3, T64, pools).
+
+    idx_given: {"main" | k: [Nb,C]} argmax positions to continue from in the main chain / the sub-network
+    of size k (oracle/pointnet.py, module docstring); pools: the same keys -> (own argmax, own maximum,
+    the stored tensor the maximum is taken over), for checking such positions.
 
     T_given: {k: [Nb,k,k]} replaces the stored matrix of a sub-network by a given one (the value a
     device run stored) from there on: a matrix entry near 1 has a storage ulp of 2^-8 in bf16, and
     one such last-bit difference moves every point of the cloud, after which the two runs take
     different argmax / ReLU decisions.  T3 / T64 in the result are the oracle's own matrices."""
     T_given = T_given or {}
+    idx_given = idx_given or {}
     s = tspec.cls
     S = lambda v: ops.store(v, s.dtype)
     lp = pn.rounded_params(theta, s.dtype)
@@ -66,13 +71,14 @@ def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None,
     x = np.asarray(points, np.float64)
     sv3 = sv64 = None
     if tspec.input_transform:
-        x, sv3 = _transform_fwd(tspec, 3, lp, x, running, new_running, fused_tail, S, T_given.get(3))
+        x, sv3 = _transform_fwd(tspec, 3, lp, x, running, new_running, S, T_given.get(3), idx_given.get(3))
     cfg0 = pn.chain_cfg(s, conv=s.conv[:2], fc=None)
     x1, ctx0 = pn.chain_fwd(cfg0, lp, x, None, running, new_running)
     if tspec.feature_transform:
-        x1, sv64 = _transform_fwd(tspec, s.conv[1], lp, x1, running, new_running, fused_tail, S, T_given.get(s.conv[1]))
-    cfg1 = pn.chain_cfg(s, conv=s.conv[1:], conv_base=1, fused_tail=fused_tail)
-    logits, ctx1 = pn.chain_fwd(cfg1, lp, x1, drop_mask, running, new_running)
+        x1, sv64 = _transform_fwd(tspec, s.conv[1], lp, x1, running, new_running, S, T_given.get(s.conv[1]),
+                                  idx_given.get(s.conv[1]))
+    cfg1 = pn.chain_cfg(s, conv=s.conv[1:], conv_base=1)
+    logits, ctx1 = pn.chain_fwd(cfg1, lp, x1, drop_mask, running, new_running, idx_given=idx_given.get("main"))
     loss, dlogits = ops.softmax_xent(logits, labels)
 
     grads: Dict[str, np.ndarray] = {}
@@ -82,13 +88,17 @@ def forward_backward(tspec, theta, points, labels, drop_mask=None, running=None,
     d = pn.chain_bwd(cfg0, lp, ctx0, d, grads, None, want_dx=tspec.input_transform)
     if tspec.input_transform:
         _transform_bwd(lp, sv3, d, grads, S, False)
+    pools = {"main": (ctx1["idx_own"], ctx1["pooled_own"], ctx1["act"])}
+    for k, sv in ((3, sv3), (s.conv[1], sv64)):
+        if sv is not None:
+            pools[k] = (sv[1]["idx_own"], sv[1]["pooled_own"], sv[1]["act"])
     return dict(loss=loss, logits=logits, grads=grads, running=new_running,
-                T3=None if sv3 is None else sv3[4], T64=None if sv64 is None else sv64[4])
+                T3=None if sv3 is None else sv3[4], T64=None if sv64 is None else sv64[4], pools=pools)
 
 
-def train_step(tspec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, fused_tail=True, T_given=None):
+def train_step(tspec, state, points, labels, hp: Dict[str, float], t: int, drop_mask=None, T_given=None, idx_given=None):
     """One fwd + bwd + Adam step of one model; updates ``state`` (see oracle/pointnet.py) in place."""
-    out = forward_backward(tspec, state["theta"], points, labels, drop_mask, state["running"], fused_tail, T_given)
+    out = forward_backward(tspec, state["theta"], points, labels, drop_mask, state["running"], T_given, idx_given)
     for k in state["theta"]:
         g = ops.store(out["grads"][k], "f32")
         th, m, v = ops.adam_step(state["theta"][k], g, state["m"][k], state["v"][k],
@@ -101,12 +111,12 @@ def train_step(tspec, state, points, labels, hp: Dict[str, float], t: int, drop_
     return out
 
 
-def array_train_step(tspec, states: List[dict], inp: dict, t: int, fused_tail=True, T_given=None):
-    """The array's reference: B separate unfused runs, one after another.  T_given: per model, see forward_backward."""
+def array_train_step(tspec, states: List[dict], inp: dict, t: int, T_given=None, idx_given=None):
+    """The array's reference: B separate unfused runs, one after another.  T_given, idx_given: per model, see forward_backward."""
     outs = []
     for b in range(tspec.cls.B):
         hp = {k: float(inp[k][b]) for k in ("lr", "beta1", "beta2", "eps", "wd")}
         mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
         outs.append(train_step(tspec, states[b], inp["points"][:, 3 * b:3 * b + 3, :], inp["labels"][b], hp, t,
-                               mask, fused_tail, None if T_given is None else T_given[b]))
+                               mask, None if T_given is None else T_given[b], None if idx_given is None else idx_given[b]))
     return outs

@@ -502,3 +502,24 @@ def test_point_transform_bruteforce_and_adjoints():
     # samples do not mix: changing sample 1's matrix leaves sample 0's output untouched
     t2 = t.copy(); t2[1] += 1.0
     assert np.array_equal(ops.point_transform_fwd(x, t2)[0], y[0])
+
+
+def test_bn_eval_fwd_pins():
+    """Evaluation-mode BatchNorm: torch's batch_norm with training=False (a library routine); the closed
+    form at the running estimates themselves (x = running_mean -> beta); and the link to training mode:
+    with the running estimates set to a batch's own mean and biased variance it reproduces that batch's
+    training-mode output."""
+    import torch
+    import torch.nn.functional as F
+    rng = np.random.default_rng(91)
+    x = rng.standard_normal((5, 4, 7)) * 2 + 1
+    g, b = rng.standard_normal(4), rng.standard_normal(4)
+    rm, rv = rng.standard_normal(4), rng.uniform(0.3, 2.0, 4)
+    y = ops.bn_eval_fwd(x, g, b, rm, rv, 1e-3)
+    T = lambda a: torch.tensor(a, dtype=torch.float64)
+    ref = F.batch_norm(T(x), T(rm), T(rv), T(g), T(b), training=False, eps=1e-3).numpy()
+    np.testing.assert_allclose(y, ref, rtol=0, atol=1e-13)
+    at_mean = ops.bn_eval_fwd(np.broadcast_to(rm[None, :, None], x.shape), g, b, rm, rv)
+    np.testing.assert_allclose(at_mean, np.broadcast_to(b[None, :, None], x.shape), rtol=0, atol=1e-15)
+    yt, mu, invstd, _, _ = ops.bn_fwd(x, g, b, 1e-5)
+    np.testing.assert_allclose(ops.bn_eval_fwd(x, g, b, mu, 1.0 / invstd ** 2 - 1e-5, 1e-5), yt, rtol=0, atol=1e-12)

@@ -23,12 +23,13 @@ def tiny_spec(fc_bn, p):
                               fc_bn=fc_bn, dropout_p=p, dtype="f64", n_classes=4, config_index=0)
 
 
-def torch_model_loss(spec, tp, points, labels, mask):
+def torch_model_loss(spec, tp, points, labels, mask, pool_at=None):
     a = T(points)
     for i in range(len(spec.conv) - 1):
         z = F.conv1d(a, tp[f"conv{i}.w"][:, :, None], tp[f"conv{i}.b"])
         a = F.relu(F.batch_norm(z, None, None, tp[f"conv{i}.bn.g"], tp[f"conv{i}.bn.b"], training=True, eps=1e-5))
-    h = a.max(dim=2).values
+    h = a.max(dim=2).values if pool_at is None else \
+        torch.gather(a, 2, torch.tensor(np.asarray(pool_at, np.int64))[:, :, None])[:, :, 0]
     nfc = len(spec.fc) - 1
     for i in range(nfc):
         h = h @ tp[f"fc{i}.w"] + tp[f"fc{i}.b"]
@@ -41,10 +42,8 @@ def torch_model_loss(spec, tp, points, labels, mask):
     return F.cross_entropy(h, torch.tensor(np.asarray(labels, np.int64))), h
 
 
-@pytest.mark.parametrize("fc_bn,p,fused_tail", [(True, 0.3, False), (False, 0.0, False), (True, 0.3, True)])
-def test_forward_backward_vs_autograd(fc_bn, p, fused_tail):
-    """``fused_tail`` only changes where storage rounding happens: in float64 it must give the
-    same loss, logits and gradients (checked against autograd like the unfused reading)."""
+@pytest.mark.parametrize("fc_bn,p", [(True, 0.3), (False, 0.0)])
+def test_forward_backward_vs_autograd(fc_bn, p):
     spec = tiny_spec(fc_bn, p)
     inp = hi.pointnet_cls_inputs(spec, seed=5)
     for b in range(spec.B):
@@ -52,7 +51,7 @@ def test_forward_backward_vs_autograd(fc_bn, p, fused_tail):
                  for k, v in inp["params"][b].items()}
         pts = inp["points"][:, 3 * b:3 * b + 3, :]
         mask = None if inp["drop_mask"] is None else inp["drop_mask"][b]
-        out = opn.forward_backward(spec, theta, pts, inp["labels"][b], mask, fused_tail=fused_tail)
+        out = opn.forward_backward(spec, theta, pts, inp["labels"][b], mask)
         tp = {k: T(v).requires_grad_() for k, v in theta.items()}
         loss, logits = torch_model_loss(spec, tp, pts, inp["labels"][b], mask)
         loss.backward()
@@ -134,3 +133,27 @@ def test_inputs_recipe():
     u = c1["points"].view(np.uint32)
     assert np.all(u & 0xFFFF == 0)
     assert c1["drop_mask"].shape == (2, 2, 256) and 0.5 < c1["drop_mask"].mean() < 0.9
+
+
+def test_given_argmax():
+    """Handing the oracle its own argmax changes nothing; handing it other positions gives the model
+    whose global feature is read at those positions (checked against autograd on torch.gather)."""
+    spec = tiny_spec(True, 0.3)
+    inp = hi.pointnet_cls_inputs(spec, seed=8)
+    theta = {k: v.astype(np.float64) for k, v in inp["params"][0].items()}
+    pts, lab, mask = inp["points"][:, 0:3, :], inp["labels"][0], inp["drop_mask"][0]
+    own = opn.forward_backward(spec, theta, pts, lab, mask)
+    same = opn.forward_backward(spec, theta, pts, lab, mask, idx_given=own["pool_idx"])
+    assert same["loss"] == own["loss"] and all(np.array_equal(same["grads"][k], own["grads"][k]) for k in theta)
+    assert np.array_equal(np.take_along_axis(own["last_act"], own["pool_idx"][:, :, None].astype(np.int64), axis=2)[:, :, 0],
+                          own["pooled"])
+    other = (own["pool_idx"] + 1) % spec.L
+    out = opn.forward_backward(spec, theta, pts, lab, mask, idx_given=other)
+    assert np.array_equal(out["pool_idx"], own["pool_idx"])          # the oracle's own argmax is still reported
+    tp = {k: T(v).requires_grad_() for k, v in theta.items()}
+    loss, _ = torch_model_loss(spec, tp, pts, lab, mask, pool_at=other)
+    loss.backward()
+    assert abs(out["loss"] - loss.item()) < 1e-12
+    for k in theta:
+        g = tp[k].grad.numpy()
+        assert np.abs(out["grads"][k] - g).max() <= 1e-10 * max(np.abs(g).max(), 1e-3), k

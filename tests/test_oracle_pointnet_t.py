@@ -61,9 +61,8 @@ def torch_loss(ts, tp, points, labels, mask):
     return F.cross_entropy(h, torch.tensor(np.asarray(labels, np.int64))), h
 
 
-@pytest.mark.parametrize("it,ft,fused_tail", [(True, True, True), (True, True, False), (True, False, True),
-                                              (False, True, True)])
-def test_forward_backward_vs_autograd(it, ft, fused_tail):
+@pytest.mark.parametrize("it,ft", [(True, True), (True, False), (False, True)])
+def test_forward_backward_vs_autograd(it, ft):
     ts = tiny(it, ft)
     inp = hi.pointnet_t_inputs(ts, seed=11)
     names = [n for n, _ in hi.pointnet_t_param_shapes(ts)]
@@ -72,7 +71,7 @@ def test_forward_backward_vs_autograd(it, ft, fused_tail):
         theta = {k: v.astype(np.float64) + 0.05 * np.random.default_rng(b).standard_normal(v.shape)
                  for k, v in inp["params"][b].items()}
         pts, mask = inp["points"][:, 3 * b:3 * b + 3, :], inp["drop_mask"][b]
-        out = opt.forward_backward(ts, theta, pts, inp["labels"][b], mask, fused_tail=fused_tail)
+        out = opt.forward_backward(ts, theta, pts, inp["labels"][b], mask)
         tp = {k: T(v).requires_grad_() for k, v in theta.items()}
         loss, logits = torch_loss(ts, tp, pts, inp["labels"][b], mask)
         loss.backward()
@@ -97,8 +96,7 @@ def test_identity_transform_is_the_plain_model():
         theta[f"t{k}.fc{n}.b"][:] = 0
     pts, lab, mask = inp["points"][:, 0:3, :], inp["labels"][0], inp["drop_mask"][0]
     out = opt.forward_backward(ts, theta, pts, lab, mask)
-    plain = opn.forward_backward(ts.cls, {k: v for k, v in theta.items() if not k.startswith("t")}, pts, lab, mask,
-                                 fused_tail=True)
+    plain = opn.forward_backward(ts.cls, {k: v for k, v in theta.items() if not k.startswith("t")}, pts, lab, mask)
     assert np.array_equal(out["T3"], np.broadcast_to(np.eye(3), out["T3"].shape))
     assert abs(out["loss"] - plain["loss"]) < 1e-13
     for k, g in plain["grads"].items():
@@ -138,8 +136,7 @@ def test_given_matrices():
     Nb, k2 = ts.cls.Nb, ts.cls.conv[1]
     eye = {3: np.broadcast_to(np.eye(3), (Nb, 3, 3)), k2: np.broadcast_to(np.eye(k2), (Nb, k2, k2))}
     ident = opt.forward_backward(ts, theta, pts, lab, mask, T_given=eye)
-    plain = opn.forward_backward(ts.cls, {k: v for k, v in theta.items() if not k.startswith("t")}, pts, lab, mask,
-                                 fused_tail=True)
+    plain = opn.forward_backward(ts.cls, {k: v for k, v in theta.items() if not k.startswith("t")}, pts, lab, mask)
     assert abs(ident["loss"] - plain["loss"]) < 1e-13
     for k, g in plain["grads"].items():
         if not k.startswith("conv0."):
