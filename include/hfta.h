@@ -130,6 +130,19 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                      const void* X, const int64_t xs[4], const void* W, const void* bias,
                      void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
 
+/* The same convolution with a per-(sample, channel) term in place of the per-channel bias (rows
+ * "Conv1d" and the element-wise rows; used where the layer's input is a concatenation of per-point
+ * feature maps with vectors tiled along the points: the tiled part's product with its block of the
+ * weights does not depend on the point, so it is computed once per sample and enters here):
+ *   Y[b,n,o,l] = act(S[b,n,o] + sum_c W[b,o,c] X[b,n,c,l]),   S: [b][n][o] with strides ss[3], ss[2] == 1,
+ * storage dtype; the sum is formed in the fp32 accumulator and stored once (no separate pass over Y,
+ * where hfta_add_sample_bias would re-read and re-round it).  A per-channel bias, if any, is part of S.
+ * Other arguments, layouts and errors as hfta_conv1x1_fwd. */
+int hfta_conv1x1_fwd_sample_bias(int B, int Nb, int Ci, int Co, int L, int dtype,
+                                 const void* X, const int64_t xs[4], const void* W,
+                                 const void* S, const int64_t ss[3],
+                                 void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
+
 /* Backward: dX[b,n,c,l] = sum_o W[b,o,c] dY[b,n,o,l]   (storage dtype, strides dxs; NULL = skip)
  *           dW[b,o,c]   = sum_{n,l} dY[b,n,o,l] X[b,n,c,l]   (fp32; NULL = skip)
  *           dbias[b,o]  = sum_{n,l} dY[b,n,o,l]              (fp32; NULL = skip)
@@ -184,7 +197,8 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
                             void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Fused BatchNorm, training mode (rows "BatchNorm1d", "BatchNorm2d").
+ * Fused BatchNorm (rows "BatchNorm1d", "BatchNorm2d"): training mode here, evaluation mode in
+ * hfta_bn_eval_fwd below.
  *   X, Y: logical [B][Nb][C][L] with strides xs / ys; supported layouts:
  *   stride_l == 1 (conv family; L = H*W for 2d) or L == 1 && stride_c == 1
  *   (the table's [N, B, C] case).  gamma, beta, running_*, save_*: fp32 [B][C].
@@ -200,6 +214,16 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype,
                 float eps, float momentum, float* running_mean, float* running_var,
                 float* save_mean, float* save_invstd,
                 void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
+
+/* Evaluation mode of the same rows (the fused operator keeps every argument of the single-model one,
+ * its training flag included; with the flag off the running estimates replace the batch statistics):
+ *   y = act(gamma (x - running_mean) / sqrt(running_var + eps) + beta); nothing is updated or saved.
+ * Layouts, dtypes and activations as hfta_bn_fwd; X is read once, Y written once; Y may alias X.
+ * EINVAL on null pointers or non-positive sizes; EUNSUPPORTED for other layouts or activations. */
+int hfta_bn_eval_fwd(int B, int Nb, int C, int L, int dtype,
+                     const void* X, const int64_t xs[4], const float* gamma, const float* beta,
+                     const float* running_mean, const float* running_var, float eps,
+                     void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
 
 /* Backward of hfta_bn_fwd including its fused activation (ReLU / LeakyReLU / NONE):
  * the activation mask is recomputed from X and the saved statistics in fp32,
@@ -270,9 +294,12 @@ int hfta_bn_bwd_maxpool(int B, int Nb, int C, int L, int dtype,
  * Outputs: V (storage dtype) and idx (int32), both with strides vs; save_mean, save_invstd; updated
  * running statistics (if given); zhit fp32 [B][Nb][Co] = the convolution output at the argmax;
  * saved_moments fp32, hfta_conv1x1_bn_maxpool_saved_floats(B, Ci, Co) floats, or NULL: what the
- * backward can reuse (Gram matrix, sums of X, W times the Gram matrix).  idx is the first point
- * that attains the maximum of the activated value up to fp32 rounding of the matrix product; among
- * points whose activated values are equal (e.g. all clipped by a ReLU) any may be returned.
+ * backward can reuse (Gram matrix, sums of X, W times the Gram matrix).  idx is the lowest point
+ * index that attains the maximum of the activated value, the maximum being decided on the fp32
+ * matrix product (so against an exact evaluation the index can differ only where two points' values
+ * lie within the product's rounding error, Ci * 2^-24 * sum_ci |W||X| scaled by |gamma| * invstd);
+ * a row whose activated values are all equal (every point clipped by a ReLU, or gamma = 0) returns
+ * index 0 and zhit at point 0.
  * act: NONE, RELU, or LEAKY with slope >= 0 (the argmax needs a non-decreasing activation).
  *
  * Backward.  Give exactly one of Z (the stored convolution output, strides zs, read ONLY at the

@@ -26,8 +26,11 @@ over points can legitimately differ between two implementations at near-ties,
 and from there on the two would differentiate different functions.  A chain-level
 comparison therefore may hand the oracle the argmax another implementation took
 (after checking it against the oracle's own values): the pooled feature is then
-read at those positions and the backward scatters there.  Without it the oracle
-uses its own argmax (lowest index among equal stored values).
+read at those positions and the backward scatters there.  Given as a pair
+(argmax, pooled values) the oracle also continues from that pooled tensor (after
+the caller has checked it against the oracle's own maximum), so that what follows
+the max over points is compared on identical inputs.  Without it the oracle uses
+its own argmax (lowest index among equal stored values).
 """
 from __future__ import annotations
 
@@ -99,8 +102,11 @@ def chain_fwd(cfg, lp, a, drop_mask=None, running=None, new_running=None, bn_eps
     pooled, idx = ops.maxpool_points_fwd(a)
     ctx["idx_own"], ctx["pooled_own"] = idx, pooled
     if idx_given is not None:
-        idx = np.asarray(idx_given)
-        pooled = np.take_along_axis(a, idx[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+        if isinstance(idx_given, tuple):
+            idx, pooled = np.asarray(idx_given[0]), np.asarray(idx_given[1], np.float64)
+        else:
+            idx = np.asarray(idx_given)
+            pooled = np.take_along_axis(a, idx[:, :, None].astype(np.int64), axis=2)[:, :, 0]
     ctx["idx"], ctx["pooled"] = idx, pooled
 
     h = pooled

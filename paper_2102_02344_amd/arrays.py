@@ -843,8 +843,8 @@ class FusedPointNetSeg(ParamArena):
 
     Nothing is copied to concatenate: every per-point layer writes its activation into its channel
     slice of one ``[Nb, B*c_point, L]`` buffer (strides), the head's first convolution reads that
-    buffer as one 2880-channel input, and the tiled part enters as ``[global | one-hot] @ Wg`` once per
-    sample, broadcast along the points.  Backward mirrors it: the head's data gradient lands in a
+    buffer as one 2880-channel input, and the tiled part enters as ``[global | one-hot] @ Wg + bias`` once
+    per sample, added in that convolution's accumulators as a per-(sample, channel) bias.  Backward mirrors it: the head's data gradient lands in a
     buffer of the same shape, and each per-point layer adds its slice to the gradient from the
     next layer."""
 
@@ -958,18 +958,20 @@ class FusedPointNetSeg(ParamArena):
         hb.maxpool_points(B, Nb, C4, L, dt, x, cst, self.gfeat, self.pool_idx, self.gvs)
         P("maxpool_points", x=xv, v=self.gfeat[:, :, :C4], idx=self.pool_idx[:, :, :C4])
         # ---- head: first layer = per-point block over the concatenation + once-per-sample block
-        hb.linear_fwd_ws(B, Nb, Cg, H[1], dt, self.gfeat, self.w("head0.wg"), None, self.hg, workspace=self.ws)
-        P("linear_fwd", layer="head0.wg", x=self.gfeat, w=self.w("head0.wg"), y=self.hg)
+        # the tiled block's product (with the layer's bias) once per sample ...
+        hb.linear_fwd_ws(B, Nb, Cg, H[1], dt, self.gfeat, self.w("head0.wg"), self.w("head0.b"), self.hg, workspace=self.ws)
+        P("linear_fwd", layer="head0.wg", x=self.gfeat, w=self.w("head0.wg"), b=self.w("head0.b"), y=self.hg)
         h, hs, hv, ci = self.cat, cst, self.cat, Cp
         for i in range(self.nh):
             co, k = H[i + 1], f"head{i}"
             cs = _cs(B, co, L)
-            hb.conv1x1_fwd(B, Nb, ci, co, L, dt, h, hs, self.w(k + ".w"), self.w(k + ".b"), self.zh[i], cs)
-            P("conv1x1_fwd", layer=k, x=hv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.zh[i])
-            if i == 0:
-                zin = self.zh[0].clone() if probe is not None else None
-                hb.add_sample_bias(B, Nb, co, L, dt, self.zh[0], cs, self.hg, (Nb * co, co, 1), self.zh[0], cs)
-                P("add_sample_bias", z=zin, s=self.hg, y=self.zh[0])
+            if i == 0:      # ... enters the convolution over the per-point block as its per-sample bias: one store
+                hb.conv1x1_fwd_sample_bias(B, Nb, ci, co, L, dt, h, hs, self.w(k + ".w"), self.hg, (Nb * co, co, 1),
+                                           self.zh[i], cs)
+                P("conv1x1_fwd_sample_bias", layer=k, x=hv, w=self.w(k + ".w"), s=self.hg, y=self.zh[i])
+            else:
+                hb.conv1x1_fwd(B, Nb, ci, co, L, dt, h, hs, self.w(k + ".w"), self.w(k + ".b"), self.zh[i], cs)
+                P("conv1x1_fwd", layer=k, x=hv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.zh[i])
             if i == self.nh - 1:
                 break
             hb.bn_fwd(B, Nb, co, L, dt, self.zh[i], cs, *bn(k), eps, mom, self.running[k + ".bn.rm"],

@@ -49,6 +49,7 @@ _SIGS = {
     "hfta_linear_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
     "hfta_linear_bwd": (_i, [_i, _i, _i, _i, _i, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_conv1x1_fwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _s4, _i, _f, _p]),
+    "hfta_conv1x1_fwd_sample_bias": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _i, _f, _p]),
     "hfta_conv1x1_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _p, _p, _p, _sz, _p]),
     "hfta_conv2d_grouped_fwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _i, _f, _p, _sz, _p]),
@@ -57,6 +58,7 @@ _SIGS = {
     "hfta_conv2d_grouped_bwd_workspace_bytes": (_sz, [_i] * 11),
     "hfta_conv2d_grouped_bwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_bn_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
+    "hfta_bn_eval_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _p, _f, _p, _s4, _i, _f, _p]),
     "hfta_bn_bwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_bn_fwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
@@ -193,6 +195,12 @@ def conv1x1_fwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Y, ys, act=ACT_NONE, ac
                                  _strides(ys), act, act_slope, _stream(stream)), "hfta_conv1x1_fwd")
 
 
+def conv1x1_fwd_sample_bias(B, Nb, Ci, Co, L, dtype, X, xs, W, S, ss, Y, ys, act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_conv1x1_fwd_sample_bias(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(S),
+                                             _strides(ss, 3), _ptr(Y), _strides(ys), act, act_slope, _stream(stream)),
+           "hfta_conv1x1_fwd_sample_bias")
+
+
 def conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype) -> int:
     return _lib.hfta_conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype)
 
@@ -237,6 +245,13 @@ def bn_fwd(B, Nb, C_, L, dtype, X, xs, gamma, beta, eps, momentum, running_mean,
     _check(_lib.hfta_bn_fwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(gamma), _ptr(beta), eps, momentum,
                             _ptr(running_mean), _ptr(running_var), _ptr(save_mean), _ptr(save_invstd), _ptr(Y),
                             _strides(ys), act, act_slope, _stream(stream)), "hfta_bn_fwd")
+
+
+def bn_eval_fwd(B, Nb, C_, L, dtype, X, xs, gamma, beta, running_mean, running_var, eps, Y, ys, act=ACT_NONE,
+                act_slope=0.0, stream=None):
+    _check(_lib.hfta_bn_eval_fwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(gamma), _ptr(beta), _ptr(running_mean),
+                                 _ptr(running_var), eps, _ptr(Y), _strides(ys), act, act_slope, _stream(stream)),
+           "hfta_bn_eval_fwd")
 
 
 def bn_bwd(B, Nb, C_, L, dtype, X, xs, dY, dys, gamma, beta, save_mean, save_invstd, dX, dxs, dgamma, dbeta,

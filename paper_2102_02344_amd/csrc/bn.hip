@@ -224,6 +224,47 @@ bool vec_ok(const void* p, const int64_t* s, int L, int dtype) {
   return L % 4 == 0 && reinterpret_cast<uintptr_t>(p) % bytes == 0 && s[0] % 4 == 0 && s[1] % 4 == 0 && s[2] % 4 == 0;
 }
 
+// Evaluation mode: y = act(gamma (x - running_mean) / sqrt(running_var + eps) + beta), one read and one
+// write; the channel's scale and shift are formed once per workgroup.
+struct BnEvalArgs {
+  const void* X; void* Y;
+  const float* gamma; const float* beta; const float* running_mean; const float* running_var;
+  int64_t xsb, xsn, xsc, ysb, ysn, ysc;
+  int Nb, C, L, act;
+  float eps, slope;
+};
+
+template <typename T, int VEC, int NT>
+__global__ __launch_bounds__(NT) void bn_eval_conv_kernel(BnEvalArgs p) {
+  const int c = blockIdx.x, b = blockIdx.y, k = b * p.C + c;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
+  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
+  const float mean = p.running_mean[k];
+  const float scale = p.gamma[k] * (1.0f / sqrtf(p.running_var[k] + p.eps)), bt = p.beta[k];
+  const int chunks = p.L / VEC;
+  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
+    float v[VEC];
+    load_vec<T, VEC>(x + w.n * p.xsn + w.ch * VEC, v);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) v[e] = apply_act(fmaf(scale, v[e] - mean, bt), p.act, p.slope);
+    store_vec<T, VEC>(y + w.n * p.ysn + w.ch * VEC, v);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(BNL_C * BNL_N) void bn_eval_linear_kernel(BnEvalArgs p) {
+  const int tx = threadIdx.x % BNL_C, ty = threadIdx.x / BNL_C;
+  const int c = blockIdx.x * BNL_C + tx, b = blockIdx.y;
+  if (c >= p.C) return;
+  const int k = b * p.C + c;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c;
+  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c;
+  const float mean = p.running_mean[k];
+  const float scale = p.gamma[k] * (1.0f / sqrtf(p.running_var[k] + p.eps)), bt = p.beta[k];
+  for (int n = ty; n < p.Nb; n += BNL_N)
+    Elem<T>::store(y + n * p.ysn, apply_act(fmaf(scale, Elem<T>::load(x + n * p.xsn) - mean, bt), p.act, p.slope));
+}
+
 int layout_kind(const int64_t* s, int L) {
   if (s[3] == 1) return 1;                 // conv family
   if (L == 1 && s[2] == 1) return 2;       // linear family
@@ -265,6 +306,38 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   if (dtype == HFTA_BF16) { if (v4) HFTA_BN_FWD(bf16_raw, 4); else HFTA_BN_FWD(bf16_raw, 1); }
   else { if (v4) HFTA_BN_FWD(float, 4); else HFTA_BN_FWD(float, 1); }
 #undef HFTA_BN_FWD
+  return launch_status();
+}
+
+int hfta_bn_eval_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
+                     const float* beta, const float* running_mean, const float* running_var, float eps, void* Y,
+                     const int64_t ys[4], int act, float act_slope, void* stream) {
+  if (B <= 0 || Nb <= 0 || C <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !gamma || !beta || !running_mean ||
+      !running_var || !Y || !ys || !(eps >= 0.f))
+    return HFTA_EINVAL;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (B > 65535) return HFTA_EUNSUPPORTED;
+  const bool lin = (L == 1 && xs[2] == 1 && ys[2] == 1);
+  const int kx = lin ? 2 : layout_kind(xs, L), ky = lin ? 2 : layout_kind(ys, L);
+  if (kx == 0 || kx != ky) return HFTA_EUNSUPPORTED;
+  BnEvalArgs a{X, Y, gamma, beta, running_mean, running_var, xs[0], xs[1], xs[2], ys[0], ys[1], ys[2],
+               Nb, C, L, act, eps, act_slope};
+  hipStream_t st = as_stream(stream);
+  if (kx == 2) {
+    dim3 grid((unsigned)((C + BNL_C - 1) / BNL_C), (unsigned)B);
+    if (dtype == HFTA_BF16) hipLaunchKernelGGL(bn_eval_linear_kernel<bf16_raw>, grid, dim3(BNL_C * BNL_N), 0, st, a);
+    else hipLaunchKernelGGL(bn_eval_linear_kernel<float>, grid, dim3(BNL_C * BNL_N), 0, st, a);
+    return launch_status();
+  }
+  dim3 grid((unsigned)C, (unsigned)B);
+  const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
+  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
+#define HFTA_BN_EVAL(T, V) \
+  do { if (big) hipLaunchKernelGGL((bn_eval_conv_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a); \
+       else hipLaunchKernelGGL((bn_eval_conv_kernel<T, V, 256>), grid, dim3(256), 0, st, a); } while (0)
+  if (dtype == HFTA_BF16) { if (v4) HFTA_BN_EVAL(bf16_raw, 4); else HFTA_BN_EVAL(bf16_raw, 1); }
+  else { if (v4) HFTA_BN_EVAL(float, 4); else HFTA_BN_EVAL(float, 1); }
+#undef HFTA_BN_EVAL
   return launch_status();
 }
 

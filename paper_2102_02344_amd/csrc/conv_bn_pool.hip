@@ -931,8 +931,26 @@ __global__ __launch_bounds__(256) void fbp_finish_kernel(FbpArgs p, int tiles) {
   }
   const int k = b * p.Co + c;
   const float g = p.gamma[k];
-  const float z = (g < 0.f ? -best : best) + (p.bias ? bf16_to_f32(p.bias[k]) : 0.f);
-  const float y = apply_act(fmaf(g * p.save_invstd[k], z - p.save_mean[k], p.beta[k]), p.act, p.slope);
+  const float bias = p.bias ? bf16_to_f32(p.bias[k]) : 0.f;
+  const float scale = g * p.save_invstd[k], mean = p.save_mean[k], beta = p.beta[k];
+  float z = (g < 0.f ? -best : best) + bias;
+  float pre = fmaf(scale, z - mean, beta);
+  // Equal activated values: the maximum is taken over act(BatchNorm(z)), so where the activation
+  // is flat (ReLU, or LeakyReLU with slope 0, at a maximum that is not positive) or the channel's
+  // scale is zero, every point of the row holds the same value and the lowest index, 0, is the
+  // argmax.  z at point 0 is recomputed here (Ci products) since no slice kept it.
+  const bool flat = g == 0.f || ((p.act == HFTA_ACT_RELU || (p.act == HFTA_ACT_LEAKY && p.slope == 0.f)) && !(pre > 0.f));
+  if (flat && at != 0) {
+    const bf16_raw* x0 = p.X + b * p.xsb + n * p.xsn;
+    const bf16_raw* w = p.W + (int64_t)k * p.Ci;
+    float acc = 0.f;
+    for (int ci = 0; ci < p.Ci; ++ci) acc = fmaf(bf16_to_f32(w[ci]), bf16_to_f32(x0[ci * p.xsc]), acc);
+    at = 0;
+    z = acc + bias;
+    pre = fmaf(scale, z - mean, beta);
+    if ((p.act == HFTA_ACT_RELU || (p.act == HFTA_ACT_LEAKY && p.slope == 0.f)) && pre > 0.f) pre = 0.f;   // the row's maximum was not positive
+  }
+  const float y = apply_act(pre, p.act, p.slope);
   p.V[b * p.vsb + n * p.vsn + c * p.vsc] = f32_to_bf16(y);
   p.idx[b * p.vsb + n * p.vsn + c * p.vsc] = at;
   p.zhit[bn * p.Co + c] = z;

@@ -421,6 +421,28 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
   return gemm_launch(d, as_stream(stream));
 }
 
+// A k=1 convolution over [per-point maps | a vector tiled along the points] is the convolution over the
+// per-point maps plus, per sample, the tiled vector's product with its block of the weights: that
+// per-(sample, channel) term enters here as the accumulators' bias, so the sum is stored (rounded) once
+// and no pass over Y adds it afterwards.
+int hfta_conv1x1_fwd_sample_bias(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                                 const void* W, const void* S, const int64_t ss[3], void* Y, const int64_t ys[4], int act,
+                                 float act_slope, void* stream) {
+  int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
+  if (rc != HFTA_OK) return rc;
+  if (!X || !W || !S || !Y || !xs || !ss || !ys || !valid_act(act)) return HFTA_EINVAL;
+  if (xs[3] != 1 || ys[3] != 1 || ss[2] != 1) return HFTA_EUNSUPPORTED;
+  GemmDesc d = base_desc(dtype);
+  d.A = W; d.Bm = X; d.C = Y;
+  d.M = Co; d.N = L; d.K = Ci; d.G0 = B; d.G1 = Nb;
+  d.a_kc = true; d.a_ld = Ci; d.a_g0 = (int64_t)Co * Ci; d.a_g1 = 0;
+  d.b_kc = false; d.b_ld = xs[2]; d.b_g0 = xs[0]; d.b_g1 = xs[1];
+  d.c_ld = ys[2]; d.c_g0 = ys[0]; d.c_g1 = ys[1];
+  d.bias = S; d.bias_mode = 1; d.bias_g0 = ss[0]; d.bias_g1 = ss[1];
+  d.act = act; d.slope = act_slope;
+  return gemm_launch(d, as_stream(stream));
+}
+
 // The data gradient of a narrow layer (Co <= 128, or Co <= 256 under at least 512 inputs) is a k=1 convolution of dY with the transposed
 // weights: it takes the streaming forward kernel once W^T [B][Ci][Co] has been written to the workspace.
 static bool dx_streams(int Ci, int Co, int L, int dtype) {

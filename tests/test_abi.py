@@ -69,6 +69,9 @@ def test_validation_precedes_launch(lib):
                            0, 0.0, None) == lib.EINVAL
     assert raw.hfta_bn_fwd(1, 2, 3, 4, 0, one, s4, one, one, 1e-5, 0.1, None, None, one, one, one, s4,
                            lib.ACT_TANH, 0.0, None) == lib.EUNSUPPORTED
+    assert raw.hfta_bn_eval_fwd(1, 2, 3, 4, 0, one, s4, one, one, one, None, 1e-5, one, s4, 0, 0.0, None) == lib.EINVAL
+    assert raw.hfta_bn_eval_fwd(1, 2, 3, 4, 0, one, bad_l, one, one, one, one, 1e-5, one, bad_l, 0, 0.0, None) == lib.EUNSUPPORTED
+    assert raw.hfta_bn_eval_fwd(1, 2, 3, 4, 0, one, s4, one, one, one, one, 1e-5, one, s4, lib.ACT_GELU, 0.0, None) == lib.EUNSUPPORTED
     assert raw.hfta_adam_step(2, 8, 0, one, one, one, one, None, one, one, one, one, one, 0, 0, None) == lib.EINVAL
     assert raw.hfta_adam_step(2, 0, 0, one, one, one, one, None, one, one, one, one, one, 1, 0, None) == lib.EINVAL
     assert raw.hfta_maxpool_points(1, 1, 1, 0, 0, one, s4, one, one, (C.c_int64 * 3)(1, 1, 1), None) == lib.EINVAL

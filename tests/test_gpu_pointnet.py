@@ -14,6 +14,8 @@ pytestmark = pytest.mark.gpu
 
 # A free-running chain accumulates the per-operator bound (1e-5 fp32, 2e-2 bf16) about
 # linearly in the number of library calls it passes through; norm-wise per tensor and model.
+from util import TOL
+
 CHAIN_TOL = {"f32": 2e-4, "bf16": 6e-2}
 
 
@@ -48,7 +50,7 @@ def run_case(spec, steps=1):
     tol = chain_tol(spec)
     for t in range(1, steps + 1):
         print(f"{spec.name}: step {t}", flush=True)
-        outs = opn.array_train_step(spec, states, inp, t, fused_tail=arr.fused_tail)
+        outs = opn.array_train_step(spec, states, inp, t)
         arr.forward_backward()
         torch.cuda.synchronize()
         loss = arr.loss.cpu().numpy()
@@ -220,12 +222,16 @@ def in_place_probe(spec, seen):
             assert np.all(np.abs(H(kw["invstd"]) - invstd) <= invstd * (1e-5 + 2e-6 * ez2 / (var + 1e-5))), "invstd"
             t3 = lambda a: a.reshape(Nb, B, C).transpose(1, 0, 2)
             check(v, t3(oops.store(rv, spec.dtype)), tol, f"{lay} pooled")
+            # ... and against the plain chain of the four single operators, each storing (rounding) its
+            # result: the merged operator stays within the per-operator tolerance of that definition
+            zs = oops.store(z, spec.dtype)
+            plain = oa.maxpool_points_fwd(B, oops.store(oops.act_fwd(oa.bn_fwd(B, zs, g, bt, 1e-5)[0], oops.ACT_RELU), spec.dtype))[0]
+            check(v, t3(plain), tol, f"{lay} pooled vs the chain of stored single operators")
             ya = oops.act_fwd(oa.bn_fwd(B, z, g, bt, 1e-5)[0], oops.ACT_RELU)
             gsel = idx.transpose(1, 0, 2).reshape(Nb, B * C, 1).astype(np.int64)
-            mism = idx != t3(ri)
-            at = np.take_along_axis(ya, gsel, axis=2)[:, :, 0]
-            assert np.all(t3(at)[mism] >= t3(rv)[mism] - 1e-5 * (np.abs(t3(rv)[mism]) + np.abs(ya).max()))
-            assert mism.mean() <= 0.02
+            from util import check_tail_argmax
+            check_tail_argmax(ya, ri, idx.transpose(1, 0, 2).reshape(Nb, B * C), oa.conv1x1_fwd(B, np.abs(x), np.abs(w), None),
+                              x.shape[1] // B, np.abs(g) * invstd, f"{lay} one-operator tail")
             zat = np.take_along_axis(z, gsel, axis=2)[:, :, 0]
             assert np.abs(H(kw["zhit"]) - t3(zat)).max() <= 1e-5 * np.abs(z).max()
         elif op == "conv1x1_bn_maxpool_bwd":
@@ -273,12 +279,40 @@ def test_c1_every_call_in_place(dtype, fused_tail):
     assert ("conv1x1_bn_maxpool_bwd" in seen) == fused and ("conv1x1_bn_maxpool_fwd" in seen) == fused
     assert len(seen) == ((4 + 4 + 1) if fused else (5 + 4 + 1)) + (3 + 2 + 1 + 1) + (1 + 2 + 3) + \
         ((1 + 4 + 4) if fused else (1 + 4 + 5))
-    # forward results of the free-running chain stay close to the oracle's free-running chain
+    # The free-running chain against the oracle's plain chain of single operators (every tensor between
+    # two operators stored, i.e. rounded): the device may merge operators (the one-operator tail keeps no
+    # [Nb, C, L] tensor and rounds nothing inside), but has to stay within the chain tolerance of that
+    # definition.  The argmax of the max over points after a chain of rounded operators can differ at
+    # near-ties: every device index is checked against the oracle's own stored activations (the value
+    # there is within the per-operator tolerance of the oracle's maximum), counted and reported, and
+    # the oracle continues from the device's indices and pooled values (checked against its own maximum
+    # below) so that both sides differentiate the same function on the same inputs.
+    torch.cuda.synchronize()
     states = [opn.init_state(inp["params"][b]) for b in range(spec.B)]
-    outs = opn.array_train_step(spec, states, inp, 1, fused_tail=arr.fused_tail)
+    idx_dev = arr.pool_idx.cpu().numpy()
+    pooled = arr.pooled.float().cpu().numpy().astype(np.float64)
+    outs = opn.array_train_step(spec, states, inp, 1, idx_given=[(idx_dev[b], pooled[b]) for b in range(spec.B)])
     loss = arr.loss.cpu().numpy()
+    tol, flips = TOL[dtype], 0
     for b in range(spec.B):
+        ya, v, own = outs[b]["last_act"], outs[b]["pooled"], outs[b]["pool_idx"]
+        at = np.take_along_axis(ya, idx_dev[b][:, :, None].astype(np.int64), axis=2)[:, :, 0]
+        assert np.all(at >= v - tol * (np.abs(v) + np.abs(ya).max())), "device argmax is not at a near-tie of the oracle's maximum"
+        flips += int((idx_dev[b] != own).sum())
+        assert np.abs(pooled[b] - v).max() <= CHAIN_TOL[dtype] * max(np.abs(v).max(), 1e-30)
         assert abs(loss[b] - outs[b]["loss"]) <= CHAIN_TOL[dtype] * abs(outs[b]["loss"])
+        if dtype != "f32":
+            continue      # bf16 gradients of a free-running chain through 4-sample BatchNorms are not comparable; every call is checked in place above
+        wmax = max(np.abs(outs[b]["grads"][n]).max() for n, _ in arr.shapes if n.endswith(".w"))
+        for name, _ in arr.shapes:
+            g = arr.param_host(arr.grad, name, b).astype(np.float64)
+            ref = outs[b]["grads"][name]
+            if zero_grad_param(spec, name):
+                assert np.abs(g).max() <= 2e-2 * wmax and np.abs(ref).max() <= 2e-2 * wmax, name
+                continue
+            errf = np.linalg.norm(g - ref) / max(np.linalg.norm(ref), 1e-30)
+            assert errf <= chain_tol(spec), (name, b, errf)
+    print(f"argmax positions that differ from the oracle's own: {flips} of {idx_dev.size} ({dtype}, fused tail: {fused})", flush=True)
 
 
 def test_c0_fp32_full_config_two_steps():

@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import hfta_inputs as hi
+from oracle import array as oa
 from oracle import ops as oops
 from oracle import pointnet_seg as oseg
 from test_gpu_pointnet import CHAIN_TOL, in_place_probe
@@ -99,8 +100,15 @@ def seg_probe(spec, seen):
         seen.append(op)
         if op == "linear_fwd":
             Fx = kw["x"].shape[2]
-            y = np.stack([oops.linear_fwd(H(kw["x"])[b], H(kw["w"]).reshape(B, Fx, -1)[b]) for b in range(B)])
+            y = np.stack([oops.linear_fwd(H(kw["x"])[b], H(kw["w"]).reshape(B, Fx, -1)[b], H(kw["b"]).reshape(B, -1)[b])
+                          for b in range(B)])
             check(H(kw["y"]), y, tol, f"{lay} fwd")
+        elif op == "conv1x1_fwd_sample_bias":
+            x, s_ = H(kw["x"]), H(kw["s"])
+            Nb, Co = s_.shape[1], s_.shape[2]
+            w = H(kw["w"]).reshape(B * Co, -1)
+            ref = oops.add_sample_bias(oa.conv1x1_fwd(B, x, w, None), s_.transpose(1, 0, 2).reshape(Nb, B * Co))
+            check(H(kw["y"]), ref, tol, f"{lay} convolution with a per-sample bias")
         elif op == "linear_bwd":
             Fx = kw["x"].shape[2]
             for b in range(B):
@@ -148,16 +156,15 @@ def test_seg_every_call_in_place_and_chain(dtype):
     B, Nb, L, Cp, Cg, co = spec.B, spec.Nb, spec.L, spec.c_point, spec.c_global, spec.head[1]
 
     def probe(op, **kw):
-        """The per-call checks, plus: the head's first layer as the device runs it (convolution over the
-        per-point block, stored; once-per-sample block, stored; their sum, stored) against the layer's
-        plain definition -- ONE k=1 convolution of the explicit concatenation with the [Co, c_point +
+        """The per-call checks, plus: the head's first layer as the device runs it (once-per-sample block
+        with the bias, stored; convolution over the per-point block with that as its per-sample bias,
+        stored) against the layer's plain definition -- ONE k=1 convolution of the explicit concatenation with the [Co, c_point +
         c_global] weight, one store -- on the bits the GPU consumed, at the per-operator tolerance."""
         inner(op, **kw)
-        if op == "conv1x1_fwd" and kw.get("layer") == "head0":
-            kept.update(x=H(kw["x"]), w=H(kw["w"]).reshape(B, co, Cp), b=H(kw["b"]).reshape(B, co))
-        elif op == "linear_fwd" and kw.get("layer") == "head0.wg":
-            kept.update(t=H(kw["x"]), wg=H(kw["w"]).reshape(B, Cg, co))
-        elif op == "add_sample_bias":
+        if op == "linear_fwd" and kw.get("layer") == "head0.wg":
+            kept.update(t=H(kw["x"]), wg=H(kw["w"]).reshape(B, Cg, co), b=H(kw["b"]).reshape(B, co))
+        elif op == "conv1x1_fwd_sample_bias":
+            kept.update(x=H(kw["x"]), w=H(kw["w"]).reshape(B, co, Cp))
             y = H(kw["y"]).reshape(Nb, B, co, L)
             for b in range(B):
                 tiled = np.broadcast_to(kept["t"][b][:, :, None], (Nb, Cg, L))
@@ -184,7 +191,7 @@ def test_seg_every_call_in_place_and_chain(dtype):
 
     arr.forward_backward(probe)
     nconv, nh = len(spec.conv) - 1, len(spec.head) - 1
-    assert len(seen) == 2 * nconv + 1 + 1 + nh + 1 + (nh - 1) + 1 + (nh - 1) + nh + 2 + 1 + (nconv - 1) + 2 * nconv
+    assert len(seen) == 2 * nconv + 1 + 1 + nh + (nh - 1) + 1 + (nh - 1) + nh + 2 + 1 + (nconv - 1) + 2 * nconv
     states = [oseg.init_state(inp["params"][b]) for b in range(spec.B)]
     outs = oseg.array_train_step(spec, states, inp, 1)
     tol = CHAIN_TOL[dtype] if dtype == "bf16" else 1e-5 * (6 * nconv + 6 * nh + 8)

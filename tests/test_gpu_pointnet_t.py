@@ -16,13 +16,18 @@ pytestmark = pytest.mark.gpu
 # calls through three BatchNorm'd heads; norm-wise per tensor and model.  The oracle continues from the
 # matrices the device stored (a last-bit difference in a bf16 matrix entry near 1 is 2^-8 relative
 # and moves every point of the cloud, after which argmax and ReLU decisions differ); the matrices
-# themselves are compared to the oracle's own within two storage ulps.  The fp32 case is the sharp one
+# themselves are compared to the oracle's own within four storage ulps.  The fp32 case is the sharp one
 # (same wiring, same entry points except the one-operator tail, which has its own tests); in bf16 the
 # error scales with the storage precision (fp32: 4e-5 observed; bf16 at 32 samples per head: 0.05-0.14 in the
-# Frobenius norm, single entries up to 0.3 where an argmax or a ReLU decision differs).
+# Frobenius norm, single entries up to 0.3 where a ReLU decision differs).  The oracle is the plain chain
+# (it stores, i.e. rounds, the convolution output and the activation of every tail, where the device's
+# one-operator tails round neither), so it also continues from the pooled features the device produced,
+# after each has been checked against the oracle's own maximum.
 TOL = {"f32": 5e-4, "bf16": 0.2}          # Frobenius norm of a gradient tensor; loss; parameters after Adam
 TOL_MAX = {"f32": 5e-4, "bf16": 0.5}     # largest entry: a flipped argmax or ReLU moves single entries
-T_TOL = {"f32": 1e-5, "bf16": 2 * 2.0 ** -7}
+# (the oracle's sub-networks are the plain chain, which stores the last per-point layer's output and its
+# activation; the device's one-operator tail rounds neither: two more storage ulps on that path)
+T_TOL = {"f32": 1e-5, "bf16": 4 * 2.0 ** -7}
 
 
 def tspec(dtype, it=True, ft=True, L=260):
@@ -63,7 +68,20 @@ def test_transform_array_against_serial_oracle(dtype, it, ft):
         loss = arr.loss.cpu().numpy()
         Tg = [{tn["k"]: tn["T"][b].float().cpu().numpy().astype(np.float64) for tn in (arr.t_in, arr.t_feat) if tn is not None}
               for b in range(ts.cls.B)]
-        outs = opt.array_train_step(ts, states, inp, t, fused_tail=arr.rest.fused_tail, T_given=Tg)
+        # ... and from the device's three max-over-points (argmax positions and pooled values, each checked
+        # against the oracle's own stored activations and maximum below; oracle/pointnet.py)
+        chains = [("main", arr.rest)] + [(tn["k"], tn["chain"]) for tn in (arr.t_in, arr.t_feat) if tn is not None]
+        Ig = [{key: (ch.pool_idx[b].cpu().numpy(), ch.pooled[b].float().cpu().numpy().astype(np.float64)) for key, ch in chains}
+              for b in range(ts.cls.B)]
+        outs = opt.array_train_step(ts, states, inp, t, T_given=Tg, idx_given=Ig)
+        ptol = 1e-5 if dtype == "f32" else 2e-2
+        for b in range(ts.cls.B):
+            for key, _ in chains:
+                own, v, ya = outs[b]["pools"][key]
+                gi, gv = Ig[b][key]
+                at = np.take_along_axis(ya, gi[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+                assert np.all(at >= v - ptol * (np.abs(v) + np.abs(ya).max())), (t, b, key)      # a near-tie of the oracle's maximum
+                assert np.abs(gv - v).max() <= 3 * ptol * max(np.abs(v).max(), 1e-30), (t, b, key)   # pooled value, chain tolerance
         for b in range(ts.cls.B):
             assert abs(loss[b] - outs[b]["loss"]) <= tol * abs(outs[b]["loss"]), (t, b, loss[b], outs[b]["loss"])
             for k, key in ((3, "T3"), (ts.cls.conv[1], "T64")):

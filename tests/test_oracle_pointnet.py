@@ -147,6 +147,8 @@ def test_given_argmax():
     assert same["loss"] == own["loss"] and all(np.array_equal(same["grads"][k], own["grads"][k]) for k in theta)
     assert np.array_equal(np.take_along_axis(own["last_act"], own["pool_idx"][:, :, None].astype(np.int64), axis=2)[:, :, 0],
                           own["pooled"])
+    pair = opn.forward_backward(spec, theta, pts, lab, mask, idx_given=(own["pool_idx"], own["pooled"]))
+    assert pair["loss"] == own["loss"] and all(np.array_equal(pair["grads"][k], own["grads"][k]) for k in theta)
     other = (own["pool_idx"] + 1) % spec.L
     out = opn.forward_backward(spec, theta, pts, lab, mask, idx_given=other)
     assert np.array_equal(out["pool_idx"], own["pool_idx"])          # the oracle's own argmax is still reported

@@ -42,3 +42,29 @@ def check(gpu, ref, tol, what="", extra=None):
     bad = d > tol * (np.abs(ref) + rms) + 1e-30
     assert not bad.any(), f"{what}: {bad.sum()} elements beyond tol; worst {d[bad].max():.3e}"
     return nw
+
+
+def check_tail_argmax(ya, ri, gi, absdot, Ci, scale, what=""):
+    """Argmax of the one-operator tail (conv -> BatchNorm -> act -> max over points) against the oracle's.
+
+    ya [N, K, L]: the oracle's activated values (float64); ri, gi [N, K]: the oracle's and the device's
+    argmax; absdot [N, K, L] = sum_c |w_c| |x_c| at every point; scale [K] = |gamma| * invstd.
+    The device decides the maximum on fp32 matrix products whose inputs are exact: a Ci-term dot product
+    carries at most Ci * 2^-24 * sum|w||x| of rounding, which BatchNorm scales by |gamma| * invstd and
+    the (1-Lipschitz) activation does not enlarge.  So wherever the indices differ, the oracle's value at
+    the device's index must be within the sum of that bound at the two positions of the oracle's
+    maximum; rows whose activated values are all equal must return index 0 (lowest index among equal
+    values).  Returns the number of differing indices."""
+    N, K, L = ya.shape
+    rv = np.take_along_axis(ya, ri[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    at = np.take_along_axis(ya, gi[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    flat = ya.max(axis=2) == ya.min(axis=2)
+    assert np.all(gi[flat] == 0), f"{what}: a row of equal activated values must return index 0"
+    bound = Ci * 2.0 ** -24 * absdot * np.asarray(scale)[None, :, None]
+    b_at = np.take_along_axis(bound, gi[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    b_ref = np.take_along_axis(bound, ri[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    mism = gi != ri
+    assert np.all(at[mism] >= rv[mism] - (b_at + b_ref)[mism]), f"{what}: argmax beyond the fp32 product's rounding bound"
+    # an exact tie of the oracle's values at a lower index than the oracle's own cannot happen; at a higher one it
+    # means the device skipped the first of two equal values only if they differ in its own arithmetic
+    return int(mism.sum())
