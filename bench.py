@@ -473,7 +473,7 @@ class Workload:
         if self.name in ("c0", "c1", "c1t"):
             i1["drop_mask"] = None if self.inp["drop_mask"] is None else self.inp["drop_mask"][b:b + 1]
         for k in self.per_model_keys + ("lr", "beta1", "beta2", "eps", "wd"):
-            i1[k] = self.inp[k][b:b + 1]
+            i1[k] = self.inp[k][b:b + 1]          # ("pos" of the Transformer workload is shared by the models)
         if self.name == "c3":
             cz = self.spec.g_layers[0][0]
             i1["z"] = np.ascontiguousarray(self.inp["z"][:, cz * b:cz * (b + 1)])

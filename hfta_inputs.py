@@ -384,9 +384,20 @@ def transformer_param_shapes(spec: TransformerSpec) -> List[Tuple[str, Tuple[int
     return out
 
 
+def position_table(S: int, E: int) -> np.ndarray:
+    """The fixed sinusoidal position table of the encoder, float32 [S, E] (an input constant of the
+    model, shared by all B models): sin(pos / 10000^(2i/E)) on even columns, cos on odd ones."""
+    pos = np.arange(S, dtype=np.float64)[:, None]
+    div = np.exp(np.arange(0, E, 2, dtype=np.float64) * (-np.log(10000.0) / E))
+    pe = np.zeros((S, E))
+    pe[:, 0::2] = np.sin(pos * div)
+    pe[:, 1::2] = np.cos(pos * div)[:, :E // 2]
+    return pe.astype(np.float32)
+
+
 def transformer_inputs(spec: TransformerSpec, seed: Optional[int] = None, perturb_ln: bool = False) -> Dict[str, object]:
     """tokens, targets int32 [B, N, S] (targets = the next token of a stream of N*S+1 uniform tokens);
-    params; lr, beta1, beta2, eps, wd [B]."""
+    pos float32 [S, E] (position_table); params; lr, beta1, beta2, eps, wd [B]."""
     seed = config_seed(spec.config_index) if seed is None else seed
     rngs = model_streams(seed, spec.B)
     B, N, S = spec.B, spec.N, spec.S
@@ -412,8 +423,9 @@ def transformer_inputs(spec: TransformerSpec, seed: Optional[int] = None, pertur
                 p[name] = np.zeros(shape, np.float32) if not perturb_ln else (0.05 * rng.standard_normal(shape)).astype(np.float32)
         params.append(p)
         lr[b] = log_uniform(rng, *spec.lr_range)
-    return dict(tokens=tokens, targets=targets, params=params, lr=lr, beta1=np.full(B, 0.9, np.float32),
-                beta2=np.full(B, 0.999, np.float32), eps=np.full(B, 1e-8, np.float32), wd=np.zeros(B, np.float32))
+    return dict(tokens=tokens, targets=targets, pos=position_table(S, spec.E), params=params, lr=lr,
+                beta1=np.full(B, 0.9, np.float32), beta2=np.full(B, 0.999, np.float32), eps=np.full(B, 1e-8, np.float32),
+                wd=np.zeros(B, np.float32))
 
 
 # --------------------------------------------------------------------------

@@ -18,7 +18,10 @@
  *    without a GPU.
  *  - Pointers are DEVICE pointers unless a comment says "host".  The caller
  *    owns all memory; the library allocates nothing, frees nothing and keeps
- *    no pointer after the call returns.  Scratch memory is a caller-supplied
+ *    no pointer after the call returns.  The only state it keeps between calls
+ *    is read-only after its first use: the compute-unit count of the device
+ *    (queried once, sizes the persistent GEMM launches) and, for
+ *    hfta_linear_fwd_static, the address of its built-in scratch array.  Scratch memory is a caller-supplied
  *    `workspace` whose required size the matching *_workspace_bytes function
  *    returns (0 = none needed; then NULL is accepted).
  *  - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =

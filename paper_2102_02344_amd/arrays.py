@@ -1072,13 +1072,7 @@ class FusedTransformerLM(ParamArena):
         self.scale = sqrt(E)
         self.tokens = torch.from_numpy(inp["tokens"].reshape(B, R)).to(self.dev)
         self.targets = torch.from_numpy(inp["targets"].reshape(B, R)).to(self.dev)
-        # the fixed position table, float32 (computed on the host in float64 by its closed form)
-        pos = torch.arange(S, dtype=torch.float64)[:, None]
-        div = torch.exp(torch.arange(0, E, 2, dtype=torch.float64) * (-np.log(10000.0) / E))
-        pe = torch.zeros(S, E, dtype=torch.float64)
-        pe[:, 0::2] = torch.sin(pos * div)
-        pe[:, 1::2] = torch.cos(pos * div)[:, :E // 2]
-        self.pos = pe.to(torch.float32).to(self.dev)
+        self.pos = torch.from_numpy(np.ascontiguousarray(inp["pos"], np.float32)).to(self.dev)   # fixed position table, an input
         self.x = [torch.empty(B, R, E, **act) for _ in range(nl + 1)]
         self.qkv = [torch.empty(B, R, 3 * E, **act) for _ in range(nl)]
         self.p = [torch.empty(B, N, Hh, S, S, **act) for _ in range(nl)]

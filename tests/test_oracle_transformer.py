@@ -124,3 +124,10 @@ def test_train_step_vs_torch_adam_and_independence():
         otr.array_train_step(s1, alone, i1, t)
     for k in alone[0]["theta"]:
         assert np.array_equal(alone[0]["theta"][k], states[1]["theta"][k]), k
+
+
+def test_position_table_input_matches_the_definition():
+    """The table the input module hands to the device is the oracle's closed form, to float32."""
+    from oracle import transformer as otr
+    for S, E in ((64, 256), (7, 10)):
+        np.testing.assert_array_equal(hi.position_table(S, E), otr.positions(S, E).astype(np.float32))
