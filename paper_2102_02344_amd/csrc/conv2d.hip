@@ -15,6 +15,19 @@
 // fp32 partials summed in a fixed order.
 #include "gemm.h"
 
+namespace hfta {
+int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
+                    const void* Wt, const void* bias, void* Y, int act, float slope, hipStream_t st);
+size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co);
+bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad);
+int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* Wt,
+               const void* dY, void* dX, void* pack, hipStream_t st);
+bool conv_ig_dw_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad);
+int conv_ig_dw_splits(int B, int Nb, int Ci, int Co, int H, int W);
+int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
+               const void* dY, float* dW, float* partial, hipStream_t st);
+}
+
 using namespace hfta;
 
 namespace {
@@ -848,6 +861,11 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   int rc = check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g);
   if (rc != HFTA_OK) return rc;
   if (!X || !Wt || !Y || !valid_act(act)) return HFTA_EINVAL;
+  // bf16, 4x4 / stride 2 / pad 1, power-of-two output grids: the sample-folded implicit GEMM (no workspace)
+  if (dtype == HFTA_BF16) {
+    rc = conv_ig_forward(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, X, Wt, bias, Y, act, act_slope, as_stream(stream));
+    if (rc != HFTA_EUNSUPPORTED) return rc;
+  }
   Lowered L;
   // images of 16x16 outputs and more fill the implicit kernel's 128-column tiles by themselves, and
   // it moves no column buffer: measured faster there; below that the sample-folded GEMM wins
@@ -868,6 +886,8 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
 
 // Regrouped weights of the implicit data gradient (optional: the kernel gathers single taps without them).
 static size_t dx_pack_bytes(int B, int Ci, int Co, int kh, int kw, int stride, int dtype, ConvGeom g) {
+  if (dtype == HFTA_BF16 && conv_ig_dx_supported(1, Ci, Co, 2 * g.Ho, 2 * g.Wo, kh, kw, stride, 1) && kh == 4 && stride == 2)
+    return conv_ig_dx_pack_bytes(B, Ci, Co);
   const bool implicit_dx = (int64_t)g.Ho * g.Wo >= 256 && Ci >= 32;
   const int kmax = kh > kw ? kh : kw, KJ = (kmax + stride - 1) / stride;
   const int64_t K = (int64_t)Co * KJ * KJ;
@@ -882,15 +902,28 @@ static size_t implicit_bwd_bytes(int B, int Nb, int Ci, int Co, int H, int W, in
   a.M = Co; a.N = Ci * kh * kw; a.K = g.Ho * g.Wo; a.S = Nb;
   finish_tiles(a, dtype);
   const int sp = dw_splits(a);
-  return sp > 1 ? (size_t)sp * B * (size_t)a.M * a.N * sizeof(float) : 0;
+  size_t need = sp > 1 ? (size_t)sp * B * (size_t)a.M * a.N * sizeof(float) : 0;
+  if (dtype == HFTA_BF16 && conv_ig_dw_supported(Nb, Ci, Co, H, W, kh, kw, stride, pad)) {
+    const int isp = conv_ig_dw_splits(B, Nb, Ci, Co, H, W);
+    const size_t ig = isp > 1 ? (size_t)isp * B * (size_t)a.M * a.N * sizeof(float) : 0;
+    if (ig > need) need = ig;
+  }
+  return need;
 }
 
-/* What the implicit-GEMM path needs (the weight gradient's split partials; may be 0). */
+static bool ig_dx_applies(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype) {
+  return dtype == HFTA_BF16 && conv_ig_dx_supported(Nb, Ci, Co, H, W, kh, kw, stride, pad);
+}
+
+/* What the implicit-GEMM path needs (the weight gradient's split partials and the data gradient's
+ * regrouped weights; may be 0). */
 size_t hfta_conv2d_grouped_bwd_min_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
                                                    int stride, int pad, int dtype) {
   ConvGeom g;
   if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
-  return implicit_bwd_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, g);
+  const size_t imp = implicit_bwd_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, g);
+  const size_t pk = ig_dx_applies(Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype) ? conv_ig_dx_pack_bytes(B, Ci, Co) : 0;
+  return pk ? align256(imp) + pk : imp;                 // regrouped weights of the data gradient behind the partials
 }
 
 /* The size that enables the column-buffer path; anything from the implicit path's own need (the
@@ -917,6 +950,28 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   if (!dY || (dX && !Wt) || (dW && !X)) return HFTA_EINVAL;
   hipStream_t st = as_stream(stream);
   Lowered L;
+  // Data gradient as an implicit GEMM over (sample, pixel) columns per parity class: its regrouped
+  // weights take the last bytes of the workspace (every other user starts at its front, and both the
+  // minimum and the full size leave that room).
+  if (dX && workspace && ig_dx_applies(Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype)) {
+    const size_t pk = align256(conv_ig_dx_pack_bytes(B, Ci, Co));
+    const size_t need = hfta_conv2d_grouped_bwd_min_workspace_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype);
+    const size_t end = ws_bytes & ~(size_t)255;
+    if (ws_bytes >= need && end >= pk && reinterpret_cast<uintptr_t>(workspace) % 256 == 0) {
+      rc = conv_ig_dx(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, Wt, dY, dX, reinterpret_cast<unsigned char*>(workspace) + end - pk, st);
+      if (rc == HFTA_OK) dX = nullptr;
+      else if (rc != HFTA_EUNSUPPORTED) return rc;
+    }
+  }
+  // Weight gradient as an implicit GEMM over 8-channel column groups; its k-split partials start the workspace.
+  if (dW && dtype == HFTA_BF16 && conv_ig_dw_supported(Nb, Ci, Co, H, W, kh, kw, stride, pad)) {
+    const int sp = conv_ig_dw_splits(B, Nb, Ci, Co, H, W);
+    const size_t need = sp > 1 ? (size_t)sp * B * (size_t)Co * Ci * 16 * sizeof(float) : 0;
+    if (need && (!workspace || ws_bytes < need)) return HFTA_EWORKSPACE;
+    rc = conv_ig_dw(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, X, dY, dW, need ? reinterpret_cast<float*>(workspace) : nullptr, st);
+    if (rc == HFTA_OK) dW = nullptr;
+    else if (rc != HFTA_EUNSUPPORTED) return rc;
+  }
   // the data gradient of large images with enough channels stays on the implicit kernel (see the
   // forward); everything else goes through the column buffer when the workspace allows
   const bool implicit_dx = (int64_t)g.Ho * g.Wo >= 256 && Ci >= 32;

@@ -1,0 +1,595 @@
+// Grouped Conv2d / ConvTranspose2d as an implicit GEMM whose columns run over (sample, output pixel)
+// of one model (fusion rules table, rows "Conv2d" and "ConvTranspose2d": one grouped operator with
+// G = B; here the model is grid.z and never mixes with the channels).
+//
+// No column buffer exists in memory.  Per 32-element k-tile a workgroup (128 x 128 output tile, four
+// wavefronts of 64 x 64) brings the raw input patch its 128 columns need -- whole image rows, 16-byte
+// loads -- into LDS, builds the k-contiguous column tile [128 columns][32 k] from it there (LDS reads
+// of single elements, 16-byte writes), and runs the matrix instructions of the batched GEMM core on
+// it; the weight tile is an ordinary k-contiguous operand.  Folding the sample index into the columns
+// keeps the tiles full for 8x8 and 4x4 images, where a GEMM per sample has 64 or 16 columns.
+//
+//   forward (and the data gradient of a transposed convolution):
+//       Y[o][(n, y, x)] = sum_{(c, ky, kx)} W[o][(c, ky, kx)] X[n][c][s y + ky - p][s x + kx - p]
+//   data gradient (and the forward of a transposed convolution), per output-parity class (py, px):
+//       dX[c][(n, qy, qx)] = sum_{(o, jy, jx)} Wp[class][c][(o, jy, jx)] dY[n][o][qy + cy - jy][qx + cx - jx]
+//     a stride-1 correlation with a 2x2 window and the weights regrouped per class (the taps a class
+//     does not see are never multiplied); results land at (2 qy + py, 2 qx + px).
+//   weight gradient: conv_ig_dw_kernel below, dW[o][(c, ky, kx)] = sum_{(n, y, x)} dY[n][o][y][x] X[n][c][...].
+//
+// bf16 only; output grids whose width and height are powers of two; see ig_*_supported.
+#include "gemm.h"
+
+namespace hfta {
+
+namespace {
+
+constexpr int IG_MARGIN = 8;            // zero columns left of a patch row (keeps the data 16-byte aligned)
+
+struct IgClass {
+  int oy, ox;                           // patch row / column of tap (0, 0) for output (0, 0), before the margin
+  int out_y0, out_x0;                   // where the class's outputs start in the output image
+  int64_t a_off;                        // offset of the class's weights inside a model's block
+};
+
+struct IgArgs {
+  const bf16_raw* X; const bf16_raw* A; bf16_raw* Out; const bf16_raw* bias;
+  int64_t x_img, x_model;               // element strides of the view operand: sample, model (channel stride = H * W)
+  int64_t a_model;                      // weights: [b][..][m][K], K contiguous
+  int64_t o_img, o_model, o_m;          // output element strides: sample, model, GEMM row (channel)
+  int Nb, Cx, H, W;                     // view operand: channels per model, image size
+  int M, K, N;                          // GEMM sizes per model: rows, reduction, columns = Nb * Ho * Wo
+  int Ho, Wo, lgWo, lgP;                // logical output grid per sample (powers of two)
+  int sy, sx;                           // tap direction (+1 correlation, -1 mirrored)
+  int OW, oys, oxs;                     // output image width in memory, output step per grid step
+  int NI, TR, PR, PW;                   // samples per tile, grid rows per tile and sample, patch rows, patch pitch
+  int nchunk, chunk_el;                 // 16- or 8-byte pieces of patch rows per k-tile, elements per piece
+  int tiles_n, act;
+  float slope;
+  IgClass cls[4];
+};
+
+// TM: rows of the output tile (128: four wavefronts; 256: eight, the column tile is built once for
+// twice the rows -- taken when the layer has that many output channels).
+template <int KH, int KW, int S, bool SCATTER, int TM>
+__global__ __launch_bounds__(2 * TM) void conv_ig_fwd_kernel(IgArgs p) {
+  constexpr int TK = KH * KW, CPT = 32 / TK;             // taps per channel, channels per k-tile
+  constexpr int NT = 2 * TM;                             // threads
+  constexpr int A_BYTES = TM * GEMM_PITCH;               // weight tile
+  constexpr int KPT = 128 * 32 / NT;                     // k per thread of the column tile: 16 or 8
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int patch_el = CPT * p.NI * p.PR * p.PW;
+  auto As = [&](int buf) { return smem + buf * A_BYTES; };
+  auto Cb = [&](int buf) { return smem + 2 * A_BYTES + buf * GEMM_TILE_BYTES; };
+  // one patch buffer is enough: it is written before the first barrier of an iteration and read between the two
+  bf16_raw* const Pt = reinterpret_cast<bf16_raw*>(smem + 2 * A_BYTES + 2 * GEMM_TILE_BYTES);
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  const int m0 = tile_m * TM, n0 = tile_n * GEMM_BN;
+  const IgClass cl = p.cls[blockIdx.y];
+  const int b = blockIdx.z;
+  const int P = 1 << p.lgP;
+  const int img0 = n0 >> p.lgP;                          // first sample of the tile
+  const int y0 = (n0 & (P - 1)) >> p.lgWo;               // first grid row (tiles inside one sample)
+  const int HW = p.H * p.W;
+  // first patch row's image row: the smallest row any tap of grid row y0 touches
+  const int rmin = cl.oy + (p.sy < 0 ? -(KH - 1) : 0);
+  const int row_base = y0 * S + rmin;
+
+  // zero the patch once: margins, rows outside the image and samples past the batch stay zero
+  for (int i = t; i < patch_el / 2; i += NT) reinterpret_cast<uint32_t*>(Pt)[i] = 0u;
+
+  // ---- this thread's patch pieces (fixed over the k-loop up to the channel offset)
+  int64_t pg[2];                                          // global element offset of the piece at channel 0, or -1
+  int pl[2], pcl[2];                                      // LDS element offset, channel inside the k-tile
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = t + NT * i;
+    pg[i] = -1; pl[i] = 0; pcl[i] = 0;
+    if (q < p.nchunk) {
+      const int cpr = p.W / p.chunk_el;                   // pieces per image row
+      const int xc = q % cpr;
+      int r = q / cpr;
+      const int pr = r % p.PR; r /= p.PR;
+      const int il = r % p.NI, c_l = r / p.NI;
+      const int iy = row_base + pr, img = img0 + il;
+      pcl[i] = c_l;
+      pl[i] = ((c_l * p.NI + il) * p.PR + pr) * p.PW + IG_MARGIN + xc * p.chunk_el;
+      if (iy >= 0 && iy < p.H && img < p.Nb)
+        pg[i] = (int64_t)img * p.x_img + (int64_t)b * p.x_model + (int64_t)iy * p.W + xc * p.chunk_el;
+    }
+  }
+  // ---- this thread's column of the tile being built: KPT consecutive k of column t % 128
+  const int bcol = t & 127, bhalf = t >> 7;
+  int boff;                                               // patch element of tap (0, 0), channel 0 of this half
+  {
+    const int n = n0 + bcol;
+    const int il = (n >> p.lgP) - img0;
+    const int y = (n & (P - 1)) >> p.lgWo, x = n & (p.Wo - 1);
+    boff = (il * p.PR + (y - y0) * S + (cl.oy - rmin)) * p.PW + x * S + cl.ox + IG_MARGIN;
+    // first k of this thread: channel (bhalf * KPT) / TK, tap (bhalf * KPT) % TK
+    boff += ((bhalf * KPT) / TK) * (p.NI * p.PR * p.PW);
+  }
+  const int tap0 = (bhalf * KPT) % TK;
+  const int chan_el = p.NI * p.PR * p.PW;
+
+  const bf16_raw* Ab = p.A + (int64_t)b * p.a_model + cl.a_off;
+  const int ga = t & 3, ra = t >> 2;                      // rows ra and ra + TM / 2
+  uint4 qa[2], qp[2];
+  auto issue = [&](int kt) {
+    const int k = kt * 32 + ga * 8;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int m = m0 + ra + (TM / 2) * h;
+      qa[h] = (m < p.M && k + 8 <= p.K) ? *reinterpret_cast<const uint4*>(Ab + (int64_t)m * p.K + k) : make_uint4(0, 0, 0, 0);
+    }
+    const int c0 = kt * CPT;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      qp[i] = make_uint4(0, 0, 0, 0);
+      if (pg[i] >= 0 && c0 + pcl[i] < p.Cx) {
+        const bf16_raw* src = p.X + pg[i] + (int64_t)(c0 + pcl[i]) * HW;
+        if (p.chunk_el == 8) qp[i] = *reinterpret_cast<const uint4*>(src);
+        else { const uint2 v = *reinterpret_cast<const uint2*>(src); qp[i].x = v.x; qp[i].y = v.y; }
+      }
+    }
+  };
+  auto park = [&](int buf) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      *reinterpret_cast<uint4*>(As(buf) + (ra + (TM / 2) * h) * GEMM_PITCH + ga * 16) = qa[h];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      if (t + NT * i < p.nchunk && pg[i] >= 0) {
+        if (p.chunk_el == 8) *reinterpret_cast<uint4*>(Pt + pl[i]) = qp[i];
+        else *reinterpret_cast<uint2*>(Pt + pl[i]) = make_uint2(qp[i].x, qp[i].y);
+      }
+    }
+  };
+  // column tile from the patch: this thread's KPT consecutive k (taps of one or more channels) of its column
+  auto build = [&](int buf) {
+    const bf16_raw* src = Pt + boff;
+    uint32_t w[KPT / 2];
+#pragma unroll
+    for (int e = 0; e < KPT; e += 2) {
+      uint32_t v[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int kk = tap0 + e + u;                      // tap0 is 0 whenever KPT >= TK, so c_l, ty, tx fold to constants
+        const int c_l = kk / TK, tap = kk % TK, ty = tap / KW, tx = tap % KW;
+        v[u] = src[c_l * chan_el + p.sy * ty * p.PW + p.sx * tx];
+      }
+      w[e >> 1] = v[0] | (v[1] << 16);
+    }
+    unsigned char* dst = Cb(buf) + bcol * GEMM_PITCH + bhalf * KPT * 2;
+    *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    if constexpr (KPT == 16) *reinterpret_cast<uint4*>(dst + 16) = make_uint4(w[4], w[5], w[6], w[7]);
+  };
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int ktiles = (p.K + 31) / 32;
+  issue(0);
+  __syncthreads();                                        // zeroing done before any piece lands
+  park(0);
+  __syncthreads();
+  build(0);
+  if (ktiles > 1) issue(1);
+  __syncthreads();
+  int buf = 0;
+  for (int kt = 0; kt < ktiles; ++kt) {
+    const bool more = kt + 1 < ktiles;
+    if (more) park(buf ^ 1);                              // k-tile kt + 1: weights and patch
+    if (kt + 2 < ktiles) issue(kt + 2);
+    mma_tile<bf16_raw>(acc, As(buf), Cb(buf), wm, wn, lane);
+    __syncthreads();                                      // the parked patch is visible; everyone is done with As/Cb[buf]
+    if (more) build(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // ---- epilogue: bias + activation, staged through LDS, then row pieces (or single elements for a
+  // parity class, whose outputs are two elements apart)
+  unsigned char* lds = smem;
+  const bf16_raw* bias = p.bias ? p.bias + (int64_t)b * p.M : nullptr;
+  bf16_raw* ob = p.Out + (int64_t)b * p.o_model;
+#pragma unroll 1
+  for (int pass = 0; pass < TM / 128; ++pass) {           // 128 rows at a time through the staging tile
+    const int mp = m0 + 128 * pass;
+    if ((t >> 8) == pass) stage_acc<bf16_raw, bf16_raw>(acc, lds, 0, p.M, mp, bias, p.act, p.slope, t & 255);
+    __syncthreads();
+    if (!SCATTER) {
+      // 8 consecutive columns = 8 consecutive pixels of one sample: one 16-byte piece
+#pragma unroll 2
+      for (int id = t; id < 128 * 16; id += NT) {
+        const int r = id >> 4, pc = id & 15;
+        const int m = mp + r, n = n0 + pc * 8;
+        if (m >= p.M || n >= p.N) continue;
+        const int img = n >> p.lgP, pix = n & (P - 1);
+        *reinterpret_cast<uint4*>(ob + (int64_t)img * p.o_img + (int64_t)m * p.o_m + pix) =
+            *reinterpret_cast<const uint4*>(lds + r * EPI_PITCH2 + pc * 16);
+      }
+    } else {
+#pragma unroll 2
+      for (int id = t; id < 128 * 128; id += NT) {
+        const int r = id >> 7, cN = id & 127;
+        const int m = mp + r, n = n0 + cN;
+        if (m >= p.M || n >= p.N) continue;
+        const int img = n >> p.lgP, y = (n & (P - 1)) >> p.lgWo, x = n & (p.Wo - 1);
+        ob[(int64_t)img * p.o_img + (int64_t)m * p.o_m + (int64_t)(y * p.oys + cl.out_y0) * p.OW + x * p.oxs + cl.out_x0] =
+            *reinterpret_cast<const bf16_raw*>(lds + r * EPI_PITCH2 + cN * 2);
+      }
+    }
+    if (pass + 1 < TM / 128) __syncthreads();
+  }
+}
+
+int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
+bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+// patch geometry shared by the host-side checks and the launch
+bool ig_geometry(IgArgs& a, int KH, int S, int Ho, int Wo, int W) {
+  a.Ho = Ho; a.Wo = Wo; a.lgWo = ilog2(Wo); a.lgP = ilog2(Ho * Wo);
+  const int P = Ho * Wo;
+  if (P >= 128) { a.NI = 1; a.TR = 128 / Wo; } else { a.NI = 128 / P; a.TR = Ho; }
+  a.PR = (a.TR - 1) * S + KH;
+  a.chunk_el = W % 8 == 0 ? 8 : 4;
+  a.PW = W % 8 == 0 ? W + 16 : W + 12;
+  return true;
+}
+
+size_t ig_lds_bytes(const IgArgs& a, int cpt, int tm) {
+  const size_t k_loop = 2 * (size_t)tm * GEMM_PITCH + 2 * GEMM_TILE_BYTES + (size_t)cpt * a.NI * a.PR * a.PW * 2;
+  const size_t staging = 128 * (size_t)EPI_PITCH2;
+  return k_loop > staging ? k_loop : staging;
+}
+
+// Weights regrouped per output-parity class for the data gradient of a 4x4 / stride 2 / pad 1
+// convolution: Wp[b][class = 2 py + px][c][k = (o, jy, jx)] = W[b][o][c][ry + 2 jy][rx + 2 jx] with
+// ry = (py + 1) % 2 (the two taps per axis that reach pixels of that parity).
+__global__ __launch_bounds__(256) void ig_pack_class_w_kernel(const bf16_raw* __restrict__ Wt, bf16_raw* __restrict__ Wp, int Ci,
+                                                              int Co, int64_t count) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  const int K = Co * 4;
+  const int kk = (int)(i % K);
+  int64_t r = i / K;
+  const int c = (int)(r % Ci); r /= Ci;
+  const int cls = (int)(r & 3);
+  const int64_t b = r >> 2;
+  const int py = cls >> 1, px = cls & 1;
+  const int ry = (py + 1) & 1, rx = (px + 1) & 1;
+  const int o = kk >> 2, jy = (kk >> 1) & 1, jx = kk & 1;
+  Wp[i] = Wt[((b * Co + o) * Ci + c) * 16 + (ry + 2 * jy) * 4 + rx + 2 * jx];
+}
+
+
+// ---- weight gradient ---------------------------------------------------------------------------
+//   dW[o][j = (c, ky, kx)] = sum over k = (n, y, x) of dY[n][o][y][x] X[n][c][2 y + ky - 1][2 x + kx - 1]
+// Rows are output channels (dY is k-contiguous inside a sample), columns the 128 taps of 8 input
+// channels, and a k-tile is 32 consecutive output pixels (of one sample, or of two 4x4 samples).
+// The column tile [128 j][32 k] is built from the patch of the 8 channels' input rows those pixels
+// touch.  blockIdx.y splits the k range; partial sums go to fp32 slices reduced afterwards.
+struct IgDwArgs {
+  const bf16_raw* X; const bf16_raw* dY; float* Out;
+  int64_t x_img, x_model, y_img, y_model;                // element strides: sample, model
+  int64_t o_model, o_split;                              // output strides: model, k split
+  int Nb, Ci, Co, H, W, Ho, Wo, lgWo, lgP;
+  int NI, PR, PW, nchunk, chunk_el;
+  int tiles_n, kt_total, kt_per_split;
+};
+
+__global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
+  constexpr int NT = 256;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  auto As = [&](int buf) { return smem + buf * GEMM_TILE_BYTES; };
+  auto Cb = [&](int buf) { return smem + 2 * GEMM_TILE_BYTES + buf * GEMM_TILE_BYTES; };
+  bf16_raw* const Pt = reinterpret_cast<bf16_raw*>(smem + 4 * GEMM_TILE_BYTES);
+  const int chan_el = p.NI * p.PR * p.PW, patch_el = 8 * chan_el;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  const int m0 = tile_m * 128, c0 = tile_n * 8;
+  const int b = blockIdx.z;
+  const int P = 1 << p.lgP, HW = p.H * p.W;
+  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int kt_end = min(p.kt_total, kt_begin + p.kt_per_split);
+
+  for (int i = t; i < patch_el / 2; i += NT) reinterpret_cast<uint32_t*>(Pt)[i] = 0u;   // margins stay zero
+
+  // this thread's patch piece: channel, sample, patch row and position in the row are fixed; the image row moves with the k-tile
+  int p_row = 0, p_il = 0, p_lds = 0;
+  int64_t p_g = -1;
+  if (t < p.nchunk) {
+    const int cpr = p.W / p.chunk_el;
+    const int xc = t % cpr;
+    int r = t / cpr;
+    p_row = r % p.PR; r /= p.PR;
+    p_il = r % p.NI;
+    const int c_l = r / p.NI;
+    p_lds = ((c_l * p.NI + p_il) * p.PR + p_row) * p.PW + IG_MARGIN + xc * p.chunk_el;
+    if (c0 + c_l < p.Ci) p_g = (int64_t)b * p.x_model + (int64_t)(c0 + c_l) * HW + xc * p.chunk_el;
+  }
+  // this thread's part of the column tile: row j = t % 128, 16 consecutive k (pixels) as four groups of 4 in a row
+  const int bj = t & 127, bhalf = t >> 7;
+  int boff[4];
+  {
+    const int c_l = bj >> 4, ky = (bj >> 2) & 3, kx = bj & 3;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int kl = bhalf * 16 + 4 * g;
+      const int il = kl >> p.lgP, y_l = (kl & (P - 1)) >> p.lgWo, x = kl & (p.Wo - 1);
+      boff[g] = ((c_l * p.NI + il) * p.PR + 2 * y_l + ky) * p.PW + 2 * x + kx - 1 + IG_MARGIN;
+    }
+  }
+  const bf16_raw* Ab = p.dY + (int64_t)b * p.y_model;
+  const int ga = t & 3, ra = t >> 2;
+  uint4 qa[2], qp;
+  auto issue = [&](int kt) {
+    const int kk = kt * 32 + ga * 8;                      // global pixel index of this 16-byte piece
+    const int n = kk >> p.lgP, pix = kk & (P - 1);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int m = m0 + ra + 64 * h;
+      qa[h] = (m < p.Co && n < p.Nb) ? *reinterpret_cast<const uint4*>(Ab + (int64_t)n * p.y_img + (int64_t)m * P + pix)
+                                     : make_uint4(0, 0, 0, 0);
+    }
+    qp = make_uint4(0, 0, 0, 0);
+    const int kk0 = kt * 32;
+    const int img = (kk0 >> p.lgP) + p_il;
+    const int iy = 2 * ((kk0 & (P - 1)) >> p.lgWo) - 1 + p_row;
+    if (p_g >= 0 && img < p.Nb && iy >= 0 && iy < p.H) {
+      const bf16_raw* src = p.X + p_g + (int64_t)img * p.x_img + (int64_t)iy * p.W;
+      if (p.chunk_el == 8) qp = *reinterpret_cast<const uint4*>(src);
+      else { const uint2 v = *reinterpret_cast<const uint2*>(src); qp.x = v.x; qp.y = v.y; }
+    }
+  };
+  auto park = [&](int buf) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) *reinterpret_cast<uint4*>(As(buf) + (ra + 64 * h) * GEMM_PITCH + ga * 16) = qa[h];
+    if (t < p.nchunk) {
+      if (p.chunk_el == 8) *reinterpret_cast<uint4*>(Pt + p_lds) = qp;
+      else *reinterpret_cast<uint2*>(Pt + p_lds) = make_uint2(qp.x, qp.y);
+    }
+  };
+  auto build = [&](int buf) {
+    uint32_t w[8];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const bf16_raw* src = Pt + boff[g];
+      const uint32_t v0 = src[0], v1 = src[2], v2 = src[4], v3 = src[6];
+      w[2 * g] = v0 | (v1 << 16);
+      w[2 * g + 1] = v2 | (v3 << 16);
+    }
+    unsigned char* dst = Cb(buf) + bj * GEMM_PITCH + bhalf * 32;
+    *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    *reinterpret_cast<uint4*>(dst + 16) = make_uint4(w[4], w[5], w[6], w[7]);
+  };
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  if (kt_begin < kt_end) {
+    issue(kt_begin);
+    __syncthreads();
+    park(0);
+    __syncthreads();
+    build(0);
+    if (kt_begin + 1 < kt_end) issue(kt_begin + 1);
+    __syncthreads();
+    int buf = 0;
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+      const bool more = kt + 1 < kt_end;
+      if (more) park(buf ^ 1);
+      if (kt + 2 < kt_end) issue(kt + 2);
+      mma_tile<bf16_raw>(acc, As(buf), Cb(buf), wm, wn, lane);
+      __syncthreads();
+      if (more) build(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+    }
+  } else {
+    __syncthreads();
+  }
+  const int N = p.Ci * 16;
+  float* ob = p.Out + (int64_t)blockIdx.y * p.o_split + (int64_t)b * p.o_model;
+  store_tile<float, float, false>(acc, smem, ob, N, p.Co, N, m0, c0 * 16, (const float*)nullptr, 0, HFTA_ACT_NONE, 0.f, 16, t);
+}
+
+__global__ __launch_bounds__(256) void ig_split_reduce_kernel(const float4* __restrict__ partial, float4* __restrict__ out, int64_t count4, int splits) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count4) return;
+  float4 s = partial[i];
+  for (int k = 1; k < splits; ++k) {
+    const float4 v = partial[(int64_t)k * count4 + i];
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  out[i] = s;
+}
+
+constexpr size_t IG_MAX_LDS = 96 * 1024;
+
+// Kernels here take more dynamic LDS than the default limit allows: the limit of each instantiation
+// is raised before its launches (an idempotent attribute of the loaded kernel, not library state).
+template <typename K>
+void ig_launch(K kernel, dim3 grid, int threads, size_t lds, hipStream_t st, const IgArgs& a) {
+  if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)IG_MAX_LDS);
+  hipLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, st, a);
+}
+
+}  // namespace
+
+// Forward of the grouped convolution (also the data gradient of the transposed convolution).
+// HFTA_EUNSUPPORTED when the shape is outside what the kernel handles (the caller falls back).
+int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
+                    const void* Wt, const void* bias, void* Y, int act, float slope, hipStream_t st) {
+  const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+  if (kh != 4 || kw != 4 || stride != 2 || pad != 1) return HFTA_EUNSUPPORTED;
+  if (!pow2(Ho) || !pow2(Wo) || Wo < 4 || Ho * Wo < 16 || W % 4 != 0 || (128 % (Ho * Wo) != 0 && (Ho * Wo) % 128 != 0)) return HFTA_EUNSUPPORTED;
+  if ((Ho * Wo >= 128 && 128 % Wo != 0) || (int64_t)Nb * Ho * Wo > 0x7fffffff) return HFTA_EUNSUPPORTED;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(Wt) % 16 || reinterpret_cast<uintptr_t>(Y) % 16) return HFTA_EUNSUPPORTED;
+  IgArgs a{};
+  a.X = (const bf16_raw*)X; a.A = (const bf16_raw*)Wt; a.Out = (bf16_raw*)Y; a.bias = (const bf16_raw*)bias;
+  a.x_img = (int64_t)B * Ci * H * W; a.x_model = (int64_t)Ci * H * W;
+  a.a_model = (int64_t)Co * Ci * 16;
+  a.o_img = (int64_t)B * Co * Ho * Wo; a.o_model = (int64_t)Co * Ho * Wo; a.o_m = (int64_t)Ho * Wo;
+  a.Nb = Nb; a.Cx = Ci; a.H = H; a.W = W;
+  a.M = Co; a.K = Ci * 16; a.N = Nb * Ho * Wo;
+  a.sy = 1; a.sx = 1; a.OW = Wo; a.oys = 1; a.oxs = 1;
+  ig_geometry(a, 4, 2, Ho, Wo, W);
+  const int tm = Co >= 256 ? 256 : 128;
+  a.nchunk = 2 * a.NI * a.PR * (W / a.chunk_el);
+  if (a.nchunk > 2 * 2 * tm) return HFTA_EUNSUPPORTED;
+  a.tiles_n = (a.N + 127) / 128;
+  a.act = act; a.slope = slope;
+  a.cls[0] = IgClass{-pad, -pad, 0, 0, 0};
+  const size_t lds = ig_lds_bytes(a, 2, tm);
+  if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
+  const int tiles_m = (Co + tm - 1) / tm;
+  if ((int64_t)tiles_m * a.tiles_n > 0x7fffffff || B > 65535) return HFTA_EUNSUPPORTED;
+  dim3 grid((unsigned)(tiles_m * a.tiles_n), 1, (unsigned)B);
+  if (tm == 256) ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 256>, grid, 512, lds, st, a);
+  else ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 128>, grid, 256, lds, st, a);
+  return launch_status();
+}
+
+}  // namespace hfta
+
+namespace hfta {
+
+// Data gradient of the 4x4 / stride 2 / pad 1 grouped convolution (= forward of the transposed one):
+// four parity classes (grid.y), each a stride-1 2x2 correlation over dY with its regrouped weights.
+// `pack` receives the regrouped weights: conv_ig_dx_pack_bytes(...) bytes, 16-byte aligned.
+size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co) {                  // rounded up to 256 bytes
+  return ((size_t)B * 4 * Ci * Co * 4 * sizeof(bf16_raw) + 255) & ~(size_t)255;
+}
+
+bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad) {
+  if (kh != 4 || kw != 4 || stride != 2 || pad != 1 || H % 2 || W % 2) return false;
+  const int Hq = H / 2, Wq = W / 2;
+  if (!pow2(Hq) || !pow2(Wq) || Wq < 4 || Hq * Wq < 16 || (Hq * Wq >= 128 && 128 % Wq != 0)) return false;
+  if ((int64_t)Nb * Hq * Wq > 0x7fffffff || Ci < 32 || Co % 2 != 0) return false;
+  return true;
+}
+
+int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* Wt,
+               const void* dY, void* dX, void* pack, hipStream_t st) {
+  if (!conv_ig_dx_supported(Nb, Ci, Co, H, W, kh, kw, stride, pad)) return HFTA_EUNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(dY) % 16 || reinterpret_cast<uintptr_t>(Wt) % 16 || reinterpret_cast<uintptr_t>(dX) % 2 ||
+      reinterpret_cast<uintptr_t>(pack) % 16 || B > 65535)
+    return HFTA_EUNSUPPORTED;
+  const int Hq = H / 2, Wq = W / 2;                      // class grid = the gradient's own grid (Ho x Wo)
+  IgArgs a{};
+  a.X = (const bf16_raw*)dY; a.A = (const bf16_raw*)pack; a.Out = (bf16_raw*)dX; a.bias = nullptr;
+  a.x_img = (int64_t)B * Co * Hq * Wq; a.x_model = (int64_t)Co * Hq * Wq;
+  a.a_model = (int64_t)4 * Ci * Co * 4;
+  a.o_img = (int64_t)B * Ci * H * W; a.o_model = (int64_t)Ci * H * W; a.o_m = (int64_t)H * W;
+  a.Nb = Nb; a.Cx = Co; a.H = Hq; a.W = Wq;
+  a.M = Ci; a.K = Co * 4; a.N = Nb * Hq * Wq;
+  a.sy = -1; a.sx = -1; a.OW = W; a.oys = 2; a.oxs = 2;
+  ig_geometry(a, 2, 1, Hq, Wq, Wq);
+  const int tm = Ci >= 256 ? 256 : 128;
+  a.nchunk = 8 * a.NI * a.PR * (Wq / a.chunk_el);
+  if (a.nchunk > 2 * 2 * tm) return HFTA_EUNSUPPORTED;
+  a.tiles_n = (a.N + 127) / 128;
+  a.act = HFTA_ACT_NONE; a.slope = 0.f;
+  for (int cls = 0; cls < 4; ++cls) {
+    const int py = cls >> 1, px = cls & 1;
+    const int cy = py, cx = px;                           // (py + 1 - ry) / 2 with ry = (py + 1) % 2
+    a.cls[cls] = IgClass{cy, cx, py, px, (int64_t)cls * Ci * Co * 4};
+  }
+  const size_t lds = ig_lds_bytes(a, 8, tm);
+  if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
+  const int tiles_m = (Ci + tm - 1) / tm;
+  const int64_t count = (int64_t)B * 4 * Ci * Co * 4;
+  hipLaunchKernelGGL(ig_pack_class_w_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, (const bf16_raw*)Wt,
+                     (bf16_raw*)pack, Ci, Co, count);
+  dim3 grid((unsigned)(tiles_m * a.tiles_n), 4, (unsigned)B);
+  if (tm == 256) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 256>, grid, 512, lds, st, a);
+  else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128>, grid, 256, lds, st, a);
+  return launch_status();
+}
+
+}  // namespace hfta
+
+namespace hfta {
+
+// Weight gradient of the 4x4 / stride 2 / pad 1 grouped convolution.  `partial` holds the k splits'
+// fp32 slices when conv_ig_dw_splits(...) > 1 (that many times B * Co * Ci * 16 floats).
+bool conv_ig_dw_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad) {
+  if (kh != 4 || kw != 4 || stride != 2 || pad != 1 || H % 2 || W % 2) return false;
+  const int Ho = H / 2, Wo = W / 2;
+  if (!pow2(Ho) || !pow2(Wo) || Wo < 4 || Wo > 32 || Ho * Wo < 16) return false;
+  if ((int64_t)Nb * Ho * Wo > 0x7fffffff || Ci < 8 || Co < 32) return false;
+  return true;                                           // a k-tile's second 4x4 sample past the batch reads as zeros
+}
+
+int conv_ig_dw_splits(int B, int Nb, int Ci, int Co, int H, int W) {
+  const int64_t kt_total = ((int64_t)Nb * (H / 2) * (W / 2) + 31) / 32;
+  const int64_t tiles = (int64_t)((Co + 127) / 128) * ((Ci + 7) / 8) * B;
+  if (tiles >= 768 || kt_total < 32) return 1;
+  int64_t want = (1536 + tiles - 1) / tiles, cap = kt_total / 16;
+  if (want > cap) want = cap;
+  if (want > 64) want = 64;
+  return want < 1 ? 1 : (int)want;
+}
+
+int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
+               const void* dY, float* dW, float* partial, hipStream_t st) {
+  if (!conv_ig_dw_supported(Nb, Ci, Co, H, W, kh, kw, stride, pad)) return HFTA_EUNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(dY) % 16 || reinterpret_cast<uintptr_t>(dW) % 16 ||
+      reinterpret_cast<uintptr_t>(partial) % 16 || B > 65535)
+    return HFTA_EUNSUPPORTED;
+  const int Ho = H / 2, Wo = W / 2, P = Ho * Wo;
+  IgDwArgs a{};
+  a.X = (const bf16_raw*)X; a.dY = (const bf16_raw*)dY;
+  a.x_img = (int64_t)B * Ci * H * W; a.x_model = (int64_t)Ci * H * W;
+  a.y_img = (int64_t)B * Co * P; a.y_model = (int64_t)Co * P;
+  a.o_model = (int64_t)Co * Ci * 16;
+  a.Nb = Nb; a.Ci = Ci; a.Co = Co; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo;
+  a.lgWo = ilog2(Wo); a.lgP = ilog2(P);
+  a.NI = P >= 32 ? 1 : 2;
+  const int TR = P >= 32 ? 32 / Wo : Ho;
+  a.PR = (TR - 1) * 2 + 4;
+  a.chunk_el = W % 8 == 0 ? 8 : 4;
+  a.PW = W % 8 == 0 ? W + 16 : W + 12;
+  a.nchunk = 8 * a.NI * a.PR * (W / a.chunk_el);
+  if (a.nchunk > 256) return HFTA_EUNSUPPORTED;
+  a.tiles_n = (Ci + 7) / 8;
+  a.kt_total = (int)(((int64_t)Nb * P + 31) / 32);
+  const int splits = conv_ig_dw_splits(B, Nb, Ci, Co, H, W);
+  if (splits > 1 && !partial) return HFTA_EWORKSPACE;
+  a.kt_per_split = (a.kt_total + splits - 1) / splits;
+  a.o_split = (int64_t)B * a.o_model;
+  a.Out = splits > 1 ? partial : dW;
+  const size_t k_loop = 4 * (size_t)GEMM_TILE_BYTES + (size_t)8 * a.NI * a.PR * a.PW * 2;
+  const size_t staging = 64 * (size_t)EPI_PITCH4;
+  const size_t lds = k_loop > staging ? k_loop : staging;
+  if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
+  const int tiles_m = (Co + 127) / 128;
+  if (lds > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_ig_dw_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)IG_MAX_LDS);
+  hipLaunchKernelGGL(conv_ig_dw_kernel, dim3((unsigned)(tiles_m * a.tiles_n), (unsigned)splits, (unsigned)B), dim3(256), lds, st, a);
+  if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+  if (splits > 1) {
+    const int64_t count4 = (int64_t)B * a.o_model / 4;
+    hipLaunchKernelGGL(ig_split_reduce_kernel, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, st, (const float4*)partial,
+                       (float4*)dW, count4, splits);
+  }
+  return launch_status();
+}
+
+}  // namespace hfta
