@@ -135,12 +135,20 @@ def kernel_label(name, a):
         B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dt = a[:11]
         p2 = lambda v: v > 0 and v & (v - 1) == 0
         ig = dt == 1 and (kh, kw, stride, pad) == (4, 4, 2, 1) and p2(H // 2) and p2(W // 2) and W >= 8 and H * W >= 64
+        full = H == kh and W == kw and pad == 0     # whole-image window: a batched Linear
+        small = "full_%s_small_kernel" if Co <= 8 else "gemm(%s, whole-image window)"
         if name == "conv2d_grouped_fwd":       # sample-folded implicit GEMM, else the column-buffer lowering
+            if full:
+                return small % "fwd"
             return "conv_ig_fwd_kernel<4,4,2>" if ig else "conv2d fwd: im2col_lds_kernel + gemm"
         if a[14] is not None:                  # dX and dW are asked for in separate calls
-            return ("ig_pack_class_w_kernel + conv_ig_fwd_kernel<2,2,1,scatter>" if ig and Ci >= 32
+            if full:
+                return small % "dx"
+            return ("ig_pack_class_w_kernel + conv_ig_fwd_kernel<2,2,1,pair>" if ig and Ci >= 32
                     else "conv2d dX: pack_dy_kernel + gemm + col2im_lds_kernel")
-        return ("conv_ig_dw_kernel + ig_split_reduce_kernel" if ig and Ci >= 8 and Co >= 32 and W <= 64
+        if full:
+            return small % "dw"
+        return ("conv_ig_dw_kernel + ig_split_reduce_kernel" if ig and Co >= 32 and W <= 64
                 else "conv2d dW: pack_dy_kernel + im2col_lds_kernel + gemm")
     if name == "conv1x1_bwd":          # called with either dX or dW requested, never both
         B, Nb, Ci, Co, L, dt = a[:6]

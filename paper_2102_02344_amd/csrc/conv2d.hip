@@ -22,6 +22,11 @@ size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co);
 bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad);
 int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* Wt,
                const void* dY, void* dX, void* pack, hipStream_t st);
+bool conv_full_applies(int H, int W, int kh, int kw, int pad, int Ci, int Nb);
+int conv_full_fwd(int B, int Nb, int Ci, int Co, int kh, int kw, int dtype, const void* X, const void* Wt, const void* bias, void* Y,
+                  int act, float slope, hipStream_t st);
+int conv_full_dx(int B, int Nb, int Ci, int Co, int kh, int kw, int dtype, const void* Wt, const void* dY, void* dX, hipStream_t st);
+int conv_full_dw(int B, int Nb, int Ci, int Co, int kh, int kw, int dtype, const void* X, const void* dY, float* dW, hipStream_t st);
 bool conv_ig_dw_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad);
 int conv_ig_dw_splits(int B, int Nb, int Ci, int Co, int H, int W);
 int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
@@ -861,6 +866,9 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   int rc = check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g);
   if (rc != HFTA_OK) return rc;
   if (!X || !Wt || !Y || !valid_act(act)) return HFTA_EINVAL;
+  // a window that covers the whole image: the operator is a batched Linear over the flattened window
+  if (conv_full_applies(H, W, kh, kw, pad, Ci, Nb))
+    return conv_full_fwd(B, Nb, Ci, Co, kh, kw, dtype, X, Wt, bias, Y, act, act_slope, as_stream(stream));
   // bf16, 4x4 / stride 2 / pad 1, power-of-two output grids: the sample-folded implicit GEMM (no workspace)
   if (dtype == HFTA_BF16) {
     rc = conv_ig_forward(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, X, Wt, bias, Y, act, act_slope, as_stream(stream));
@@ -950,6 +958,18 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
   if (!dY || (dX && !Wt) || (dW && !X)) return HFTA_EINVAL;
   hipStream_t st = as_stream(stream);
   Lowered L;
+  if (conv_full_applies(H, W, kh, kw, pad, Ci, Nb)) {      // whole-image window: batched Linear gradients
+    if (dX) {
+      rc = conv_full_dx(B, Nb, Ci, Co, kh, kw, dtype, Wt, dY, dX, st);
+      if (rc != HFTA_OK) return rc;
+      dX = nullptr;
+    }
+    if (dW) {
+      rc = conv_full_dw(B, Nb, Ci, Co, kh, kw, dtype, X, dY, dW, st);
+      if (rc != HFTA_OK) return rc;
+      dW = nullptr;
+    }
+  }
   // Data gradient as an implicit GEMM over (sample, pixel) columns per parity class: its regrouped
   // weights take the last bytes of the workspace (every other user starts at its front, and both the
   // minimum and the full size leave that room).

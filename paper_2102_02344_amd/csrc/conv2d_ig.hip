@@ -12,13 +12,13 @@
 //   forward (and the data gradient of a transposed convolution):
 //       Y[o][(n, y, x)] = sum_{(c, ky, kx)} W[o][(c, ky, kx)] X[n][c][s y + ky - p][s x + kx - p]
 //   data gradient (and the forward of a transposed convolution), per output-parity class (py, px):
-//       dX[c][(n, qy, qx)] = sum_{(o, jy, jx)} Wp[class][c][(o, jy, jx)] dY[n][o][qy + cy - jy][qx + cx - jx]
+//       dX[c][(n, qy, qx)] = sum_{(o, jy, jx)} Wp[class][c][(o, jy, jx)] dY[n][o][qy + py - 1 + jy][qx + px - 1 + jx]
 //     a stride-1 correlation with a 2x2 window and the weights regrouped per class (the taps a class
 //     does not see are never multiplied); results land at (2 qy + py, 2 qx + px).
 //   weight gradient: conv_ig_dw_kernel below, dW[o][(c, ky, kx)] = sum_{(n, y, x)} dY[n][o][y][x] X[n][c][...].
 //
 // bf16 only; output grids whose width and height are powers of two; see ig_*_supported.
-#include "gemm.h"
+#include "gemm_pf.h"
 
 namespace hfta {
 
@@ -40,194 +40,283 @@ struct IgArgs {
   int Nb, Cx, H, W;                     // view operand: channels per model, image size
   int M, K, N;                          // GEMM sizes per model: rows, reduction, columns = Nb * Ho * Wo
   int Ho, Wo, lgWo, lgP;                // logical output grid per sample (powers of two)
-  int sy, sx;                           // tap direction (+1 correlation, -1 mirrored)
   int OW, oys, oxs;                     // output image width in memory, output step per grid step
+  int tap_step;                         // 1 (patch elements between the taps of a window row; see the column-tile build)
   int NI, TR, PR, PW;                   // samples per tile, grid rows per tile and sample, patch rows, patch pitch
   int nchunk, chunk_el;                 // 16- or 8-byte pieces of patch rows per k-tile, elements per piece
+  uint32_t x_bytes, a_bytes;            // extent of one model's slice of the view operand / of its weights
   int tiles_n, act;
   float slope;
   IgClass cls[4];
 };
 
-// TM: rows of the output tile (128: four wavefronts; 256: eight, the column tile is built once for
-// twice the rows -- taken when the layer has that many output channels).
-template <int KH, int KW, int S, bool SCATTER, int TM>
-__global__ __launch_bounds__(2 * TM) void conv_ig_fwd_kernel(IgArgs p) {
+constexpr int IG_EPI_PITCH = 128 * 2 + 16;   // bytes per staged output row (64 rows at a time)
+
+// accumulators of a wavefront (64 rows x 32 FN columns from column col0) -> staging tile [64][128]
+template <int FN>
+__device__ __forceinline__ void ig_stage64(f32x16_t (&acc)[2][FN], unsigned char* lds, int M, int mrow0, const bf16_raw* bias,
+                                           int act, float slope, int lane, int col0) {
+  const int ml = lane & 31, nq = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int rl = i * 32 + ml, m = mrow0 + rl;
+    const float bm = (bias && m < M) ? bf16_to_f32(bias[m]) : 0.f;
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = col0 + j * 32 + 8 * q + nq;
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = cheap_act(acc[i][j][4 * q + e] + bm, act, slope);
+        *reinterpret_cast<uint2*>(lds + rl * IG_EPI_PITCH + nl * 2) = make_uint2(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]));
+      }
+  }
+}
+
+// Four wavefronts; each computes 64 rows x 64 columns of a TM = 128 row tile, or 64 rows x 32 columns
+// of a TM = 64 row tile (layers with at most 64 output rows).
+// PAIR (data gradient): the tile's 128 columns are 64 pixels of the parity class px = 0 followed by
+// the same 64 pixels of px = 1 (blockIdx.y = py); the weight tile holds both classes' rows, a
+// wavefront works on the class its columns belong to, and the epilogue interleaves the two classes
+// into whole 16-byte pieces of the output rows.
+//
+// Weight tile, column tile and patch are double-buffered and there is one barrier per k-tile.  In
+// iteration kt a thread
+//   issues the LDS reads that gather its part of column tile kt+1 from patch kt+1,
+//   parks the weights of k-tile kt+1 and the patch of k-tile kt+2 (registers -> LDS),
+//   issues the loads of the weights of kt+2 and of the patch of kt+3,
+//   runs the matrix instructions on k-tile kt (the gather's reads return meanwhile),
+//   writes its part of column tile kt+1, and meets the others at the barrier.
+// Every load is a raw buffer load whose offset is inside the model's slice or the fixed out-of-range
+// value (the hardware returns zeros): no load sits under control flow, so the compiler's wait
+// counters let the loads of later k-tiles stay in flight across iterations.  Nothing in the loop
+// depends on the k-tile index: loads past the last k-tile are out of range, and what is parked or
+// built from them lands in buffers nobody reads any more.
+template <int KH, int KW, int S, bool PAIR, int TM, bool CH8>
+__global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
+  static_assert(TM == 128 || TM == 64, "row tiles of 128 or 64");
   constexpr int TK = KH * KW, CPT = 32 / TK;             // taps per channel, channels per k-tile
-  constexpr int NT = 2 * TM;                             // threads
-  constexpr int A_BYTES = TM * GEMM_PITCH;               // weight tile
-  constexpr int KPT = 128 * 32 / NT;                     // k per thread of the column tile: 16 or 8
+  constexpr int NT = 256;
+  constexpr int AROWS = PAIR ? 2 * TM : TM;              // rows of the weight tile
+  constexpr int NA = AROWS * 4 / NT;                     // 16-byte weight pieces per thread
+  constexpr int A_BYTES = AROWS * GEMM_PITCH;
+  constexpr int KPT = 16;                                // k per thread of the column tile
+  constexpr int COLS = PAIR ? 64 : 128;                  // pixel columns per tile
+  constexpr int FN = TM == 128 ? 2 : 1;                  // 32-column blocks per wavefront
+  constexpr int CH = CH8 ? 8 : 4;                        // elements per patch piece
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int patch_el = CPT * p.NI * p.PR * p.PW;
   auto As = [&](int buf) { return smem + buf * A_BYTES; };
   auto Cb = [&](int buf) { return smem + 2 * A_BYTES + buf * GEMM_TILE_BYTES; };
-  // one patch buffer is enough: it is written before the first barrier of an iteration and read between the two
-  bf16_raw* const Pt = reinterpret_cast<bf16_raw*>(smem + 2 * A_BYTES + 2 * GEMM_TILE_BYTES);
+  const int chan_el = p.NI * p.PR * p.PW;
+  const int patch_el = CPT * chan_el;
+  auto Pt = [&](int buf) { return reinterpret_cast<bf16_raw*>(smem + 2 * A_BYTES + 2 * GEMM_TILE_BYTES) + buf * patch_el; };
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
   const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
-  const int m0 = tile_m * TM, n0 = tile_n * GEMM_BN;
-  const IgClass cl = p.cls[blockIdx.y];
+  const int m0 = tile_m * TM, n0 = tile_n * COLS;
+  const IgClass cl0 = p.cls[PAIR ? 2 * blockIdx.y : 0];
   const int b = blockIdx.z;
   const int P = 1 << p.lgP;
   const int img0 = n0 >> p.lgP;                          // first sample of the tile
   const int y0 = (n0 & (P - 1)) >> p.lgWo;               // first grid row (tiles inside one sample)
   const int HW = p.H * p.W;
-  // first patch row's image row: the smallest row any tap of grid row y0 touches
-  const int rmin = cl.oy + (p.sy < 0 ? -(KH - 1) : 0);
+  const int rmin = cl0.oy;                               // first patch row's image row for grid row 0 (the same for both classes of a pair)
   const int row_base = y0 * S + rmin;
+  const int ktiles = (p.K + 31) / 32;
 
-  // zero the patch once: margins, rows outside the image and samples past the batch stay zero
-  for (int i = t; i < patch_el / 2; i += NT) reinterpret_cast<uint32_t*>(Pt)[i] = 0u;
+  // position of the wavefront's block of the tile
+  const int wm = TM == 128 ? wave >> 1 : 0;
+  const int col0 = TM == 128 ? (wave & 1) * 64 : wave * 32;
+  const int a_row0 = (PAIR ? (col0 >> 6) * TM : 0) + wm * 64;
 
-  // ---- this thread's patch pieces (fixed over the k-loop up to the channel offset)
-  int64_t pg[2];                                          // global element offset of the piece at channel 0, or -1
+  const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + (int64_t)b * p.x_model, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t rw = pf_rsrc(p.A + (int64_t)b * p.a_model, p.a_bytes);
+  // ---- patch pieces: fixed over the k-loop up to the channel, which advances CPT per k-tile.
+  // Pieces outside the image or past the batch load zeros; threads without a piece park nothing.
+  uint32_t pxo[2];                                        // byte offset of the piece at its channel of k-tile 0, or PF_OOB
   int pl[2], pcl[2];                                      // LDS element offset, channel inside the k-tile
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int q = t + NT * i;
-    pg[i] = -1; pl[i] = 0; pcl[i] = 0;
+    pxo[i] = PF_OOB; pl[i] = -1; pcl[i] = 0;
     if (q < p.nchunk) {
-      const int cpr = p.W / p.chunk_el;                   // pieces per image row
+      const int cpr = p.W / CH;                           // pieces per image row
       const int xc = q % cpr;
       int r = q / cpr;
       const int pr = r % p.PR; r /= p.PR;
       const int il = r % p.NI, c_l = r / p.NI;
       const int iy = row_base + pr, img = img0 + il;
       pcl[i] = c_l;
-      pl[i] = ((c_l * p.NI + il) * p.PR + pr) * p.PW + IG_MARGIN + xc * p.chunk_el;
+      pl[i] = ((c_l * p.NI + il) * p.PR + pr) * p.PW + IG_MARGIN + xc * CH;
       if (iy >= 0 && iy < p.H && img < p.Nb)
-        pg[i] = (int64_t)img * p.x_img + (int64_t)b * p.x_model + (int64_t)iy * p.W + xc * p.chunk_el;
+        pxo[i] = (uint32_t)(((int64_t)img * p.x_img + (int64_t)c_l * HW + (int64_t)iy * p.W + xc * CH) * 2);
     }
   }
-  // ---- this thread's column of the tile being built: KPT consecutive k of column t % 128
+  const uint32_t px_step = (uint32_t)(CPT * HW * 2);
+  // ---- column of the tile being built: KPT consecutive k of column t % 128
   const int bcol = t & 127, bhalf = t >> 7;
-  int boff;                                               // patch element of tap (0, 0), channel 0 of this half
+  int boff;                                               // patch element of tap (0, 0), first channel of this half
   {
-    const int n = n0 + bcol;
+    const IgClass cl = PAIR ? p.cls[2 * blockIdx.y + (bcol >> 6)] : cl0;
+    const int n = n0 + (PAIR ? (bcol & 63) : bcol);
     const int il = (n >> p.lgP) - img0;
     const int y = (n & (P - 1)) >> p.lgWo, x = n & (p.Wo - 1);
     boff = (il * p.PR + (y - y0) * S + (cl.oy - rmin)) * p.PW + x * S + cl.ox + IG_MARGIN;
-    // first k of this thread: channel (bhalf * KPT) / TK, tap (bhalf * KPT) % TK
-    boff += ((bhalf * KPT) / TK) * (p.NI * p.PR * p.PW);
+    boff += ((bhalf * KPT) / TK) * chan_el;
   }
-  const int tap0 = (bhalf * KPT) % TK;
-  const int chan_el = p.NI * p.PR * p.PW;
-
-  const bf16_raw* Ab = p.A + (int64_t)b * p.a_model + cl.a_off;
-  const int ga = t & 3, ra = t >> 2;                      // rows ra and ra + TM / 2
-  uint4 qa[2], qp[2];
-  auto issue = [&](int kt) {
-    const int k = kt * 32 + ga * 8;
+  // ---- weight pieces: rows ra + 64 h of the weight tile, 8 k at ga
+  const int ga = t & 3, ra = t >> 2;
+  uint32_t wo[NA];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int m = m0 + ra + (TM / 2) * h;
-      qa[h] = (m < p.M && k + 8 <= p.K) ? *reinterpret_cast<const uint4*>(Ab + (int64_t)m * p.K + k) : make_uint4(0, 0, 0, 0);
-    }
+  for (int h = 0; h < NA; ++h) {
+    const int r = ra + (NT / 4) * h;                      // PAIR: first TM rows class px = 0, then class px = 1
+    const int m = m0 + r % TM;
+    const int64_t a_off = PAIR ? p.cls[2 * blockIdx.y + r / TM].a_off : cl0.a_off;
+    wo[h] = m < p.M ? (uint32_t)((a_off + (int64_t)m * p.K + ga * 8) * 2) : PF_OOB;
+  }
+  pf_u32x4 qa[NA], qp[2];
+  auto issue_a = [&](int kt) {
+    const bool in_k = kt * 32 + ga * 8 + 8 <= p.K;
+#pragma unroll
+    for (int h = 0; h < NA; ++h)
+      qa[h] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)((in_k && wo[h] != PF_OOB) ? wo[h] + (uint32_t)kt * 64u : PF_OOB), 0, 0);
+  };
+  auto issue_p = [&](int kt) {
     const int c0 = kt * CPT;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      qp[i] = make_uint4(0, 0, 0, 0);
-      if (pg[i] >= 0 && c0 + pcl[i] < p.Cx) {
-        const bf16_raw* src = p.X + pg[i] + (int64_t)(c0 + pcl[i]) * HW;
-        if (p.chunk_el == 8) qp[i] = *reinterpret_cast<const uint4*>(src);
-        else { const uint2 v = *reinterpret_cast<const uint2*>(src); qp[i].x = v.x; qp[i].y = v.y; }
+      const uint32_t off = (c0 + pcl[i] < p.Cx && pxo[i] != PF_OOB) ? pxo[i] + (uint32_t)kt * px_step : PF_OOB;
+      if constexpr (CH8) {
+        qp[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
+      } else {
+        const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)off, 0, 0);
+        qp[i].x = v.x; qp[i].y = v.y;
       }
     }
   };
-  auto park = [&](int buf) {
+  auto park_a = [&](int buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-      *reinterpret_cast<uint4*>(As(buf) + (ra + (TM / 2) * h) * GEMM_PITCH + ga * 16) = qa[h];
+    for (int h = 0; h < NA; ++h) *reinterpret_cast<pf_u32x4*>(As(buf) + (ra + (NT / 4) * h) * GEMM_PITCH + ga * 16) = qa[h];
+  };
+  auto park_p = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      if (t + NT * i < p.nchunk && pg[i] >= 0) {
-        if (p.chunk_el == 8) *reinterpret_cast<uint4*>(Pt + pl[i]) = qp[i];
-        else *reinterpret_cast<uint2*>(Pt + pl[i]) = make_uint2(qp[i].x, qp[i].y);
+      if (pl[i] >= 0) {                                   // a store under a branch; the loads stay branch-free
+        if constexpr (CH8) *reinterpret_cast<pf_u32x4*>(Pt(buf) + pl[i]) = qp[i];
+        else *reinterpret_cast<uint2*>(Pt(buf) + pl[i]) = make_uint2(qp[i].x, qp[i].y);
       }
     }
   };
-  // column tile from the patch: this thread's KPT consecutive k (taps of one or more channels) of its column
-  auto build = [&](int buf) {
-    const bf16_raw* src = Pt + boff;
+  // column tile from the patch: this thread's 16 consecutive k (the taps of 16 / TK channels) of its column
+  // (p.tap_step is 1, passed at run time: with a constant step the compiler merges the KW adjacent
+  // elements of a window row into one 2-byte-aligned wide LDS read, which the hardware executes
+  // several times slower than the separate 2-byte reads.)
+  uint32_t bv[KPT];
+  auto build_read = [&](int buf) {
+    const bf16_raw* src = Pt(buf) + boff;
+#pragma unroll
+    for (int kk = 0; kk < KPT; ++kk) {
+      const int c_l = kk / TK, tap = kk % TK, ty = tap / KW, tx = tap % KW;
+      bv[kk] = src[c_l * chan_el + ty * p.PW + tx * p.tap_step];
+    }
+  };
+  auto build_write = [&](int buf) {
     uint32_t w[KPT / 2];
 #pragma unroll
-    for (int e = 0; e < KPT; e += 2) {
-      uint32_t v[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int kk = tap0 + e + u;                      // tap0 is 0 whenever KPT >= TK, so c_l, ty, tx fold to constants
-        const int c_l = kk / TK, tap = kk % TK, ty = tap / KW, tx = tap % KW;
-        v[u] = src[c_l * chan_el + p.sy * ty * p.PW + p.sx * tx];
-      }
-      w[e >> 1] = v[0] | (v[1] << 16);
-    }
+    for (int e = 0; e < KPT / 2; ++e) w[e] = bv[2 * e] | (bv[2 * e + 1] << 16);
     unsigned char* dst = Cb(buf) + bcol * GEMM_PITCH + bhalf * KPT * 2;
     *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
-    if constexpr (KPT == 16) *reinterpret_cast<uint4*>(dst + 16) = make_uint4(w[4], w[5], w[6], w[7]);
+    *reinterpret_cast<uint4*>(dst + 16) = make_uint4(w[4], w[5], w[6], w[7]);
   };
-
-  f32x16_t acc[2][2];
+  const int r = lane & 31, gsel = lane >> 5;
+  f32x16_t acc[2][FN];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  auto mma = [&](int buf) {
+    const unsigned char* Ab = As(buf) + (a_row0 + r) * GEMM_PITCH + gsel * 16;
+    const unsigned char* Bb = Cb(buf) + (col0 + r) * GEMM_PITCH + gsel * 16;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      bf16x8_t a[2], bq[FN];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(Ab + i * 32 * GEMM_PITCH + s * 32);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) bq[j] = *reinterpret_cast<const bf16x8_t*>(Bb + j * 32 * GEMM_PITCH + s * 32);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[j], a[i], acc[i][j], 0, 0, 0);
+    }
+  };
 
-  const int ktiles = (p.K + 31) / 32;
-  issue(0);
-  __syncthreads();                                        // zeroing done before any piece lands
-  park(0);
+  issue_a(0);
+  issue_p(0);
+  // zero both patch buffers once: the margins stay zero
+  for (int i = t; i < 2 * patch_el / 2; i += NT) reinterpret_cast<uint32_t*>(Pt(0))[i] = 0u;
   __syncthreads();
-  build(0);
-  if (ktiles > 1) issue(1);
+  park_a(0);
+  park_p(0);
+  issue_a(1);
+  issue_p(1);
   __syncthreads();
-  int buf = 0;
+  build_read(0);
+  park_p(1);
+  issue_p(2);
+  build_write(0);
+  __syncthreads();
   for (int kt = 0; kt < ktiles; ++kt) {
-    const bool more = kt + 1 < ktiles;
-    if (more) park(buf ^ 1);                              // k-tile kt + 1: weights and patch
-    if (kt + 2 < ktiles) issue(kt + 2);
-    mma_tile<bf16_raw>(acc, As(buf), Cb(buf), wm, wn, lane);
-    __syncthreads();                                      // the parked patch is visible; everyone is done with As/Cb[buf]
-    if (more) build(buf ^ 1);
+    const int buf = kt & 1;
+    build_read(buf ^ 1);                                  // gather of column tile kt + 1 (patch kt + 1 was parked an iteration ago)
+    park_a(buf ^ 1);                                      // weights kt + 1
+    park_p(buf);                                          // patch kt + 2
+    issue_a(kt + 2);
+    issue_p(kt + 3);
+    mma(buf);
+    build_write(buf ^ 1);
     __syncthreads();
-    buf ^= 1;
   }
 
-  // ---- epilogue: bias + activation, staged through LDS, then row pieces (or single elements for a
-  // parity class, whose outputs are two elements apart)
+  // ---- epilogue: bias + activation, 64 rows at a time through an LDS staging tile, then whole
+  // 16-byte pieces of the output rows
   unsigned char* lds = smem;
   const bf16_raw* bias = p.bias ? p.bias + (int64_t)b * p.M : nullptr;
   bf16_raw* ob = p.Out + (int64_t)b * p.o_model;
 #pragma unroll 1
-  for (int pass = 0; pass < TM / 128; ++pass) {           // 128 rows at a time through the staging tile
-    const int mp = m0 + 128 * pass;
-    if ((t >> 8) == pass) stage_acc<bf16_raw, bf16_raw>(acc, lds, 0, p.M, mp, bias, p.act, p.slope, t & 255);
+  for (int pass = 0; pass < TM / 64; ++pass) {
+    const int mp = m0 + 64 * pass;
+    if (wm == pass) ig_stage64<FN>(acc, lds, p.M, mp, bias, p.act, p.slope, lane, col0);
     __syncthreads();
-    if (!SCATTER) {
+    if (!PAIR) {
       // 8 consecutive columns = 8 consecutive pixels of one sample: one 16-byte piece
-#pragma unroll 2
-      for (int id = t; id < 128 * 16; id += NT) {
-        const int r = id >> 4, pc = id & 15;
-        const int m = mp + r, n = n0 + pc * 8;
+#pragma unroll
+      for (int id = t; id < 64 * 16; id += NT) {
+        const int rr = id >> 4, pc = id & 15;
+        const int m = mp + rr, n = n0 + pc * 8;
         if (m >= p.M || n >= p.N) continue;
         const int img = n >> p.lgP, pix = n & (P - 1);
         *reinterpret_cast<uint4*>(ob + (int64_t)img * p.o_img + (int64_t)m * p.o_m + pix) =
-            *reinterpret_cast<const uint4*>(lds + r * EPI_PITCH2 + pc * 16);
+            *reinterpret_cast<const uint4*>(lds + rr * IG_EPI_PITCH + pc * 16);
       }
     } else {
-#pragma unroll 2
-      for (int id = t; id < 128 * 128; id += NT) {
-        const int r = id >> 7, cN = id & 127;
-        const int m = mp + r, n = n0 + cN;
+      // 4 consecutive pixels x 2 classes = 8 consecutive output elements
+#pragma unroll
+      for (int id = t; id < 64 * 16; id += NT) {
+        const int rr = id >> 4, pc = id & 15;
+        const int m = mp + rr, n = n0 + pc * 4;
         if (m >= p.M || n >= p.N) continue;
         const int img = n >> p.lgP, y = (n & (P - 1)) >> p.lgWo, x = n & (p.Wo - 1);
-        ob[(int64_t)img * p.o_img + (int64_t)m * p.o_m + (int64_t)(y * p.oys + cl.out_y0) * p.OW + x * p.oxs + cl.out_x0] =
-            *reinterpret_cast<const bf16_raw*>(lds + r * EPI_PITCH2 + cN * 2);
+        const uint2 e = *reinterpret_cast<const uint2*>(lds + rr * IG_EPI_PITCH + pc * 8);          // px = 0
+        const uint2 o = *reinterpret_cast<const uint2*>(lds + rr * IG_EPI_PITCH + 128 + pc * 8);    // px = 1
+        const uint4 v = make_uint4((e.x & 0xffffu) | (o.x << 16), (e.x >> 16) | (o.x & 0xffff0000u),
+                                   (e.y & 0xffffu) | (o.y << 16), (e.y >> 16) | (o.y & 0xffff0000u));
+        *reinterpret_cast<uint4*>(ob + (int64_t)img * p.o_img + (int64_t)m * p.o_m + (int64_t)(y * p.oys + cl0.out_y0) * p.OW + x * p.oxs) = v;
       }
     }
-    if (pass + 1 < TM / 128) __syncthreads();
+    if (pass + 1 < TM / 64) __syncthreads();
   }
 }
 
@@ -235,25 +324,34 @@ int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 // patch geometry shared by the host-side checks and the launch
-bool ig_geometry(IgArgs& a, int KH, int S, int Ho, int Wo, int W) {
+bool ig_geometry(IgArgs& a, int KH, int S, int Ho, int Wo, int W, int cols) {
   a.Ho = Ho; a.Wo = Wo; a.lgWo = ilog2(Wo); a.lgP = ilog2(Ho * Wo);
   const int P = Ho * Wo;
-  if (P >= 128) { a.NI = 1; a.TR = 128 / Wo; } else { a.NI = 128 / P; a.TR = Ho; }
+  if (P >= cols) { a.NI = 1; a.TR = cols / Wo; } else { a.NI = cols / P; a.TR = Ho; }
   a.PR = (a.TR - 1) * S + KH;
   a.chunk_el = W % 8 == 0 ? 8 : 4;
   a.PW = W % 8 == 0 ? W + 16 : W + 12;
   return true;
 }
 
-size_t ig_lds_bytes(const IgArgs& a, int cpt, int tm) {
-  const size_t k_loop = 2 * (size_t)tm * GEMM_PITCH + 2 * GEMM_TILE_BYTES + (size_t)cpt * a.NI * a.PR * a.PW * 2;
-  const size_t staging = 128 * (size_t)EPI_PITCH2;
+// byte extents of one model's slices (buffer-load range checks); false when they do not fit 31 bits
+bool ig_extents(IgArgs& a) {
+  const int64_t xb = ((int64_t)(a.Nb - 1) * a.x_img + (int64_t)a.Cx * a.H * a.W) * 2, ab = a.a_model * 2;
+  if (xb >= ((int64_t)1 << 31) || ab >= ((int64_t)1 << 31)) return false;
+  a.x_bytes = (uint32_t)xb; a.a_bytes = (uint32_t)ab;
+  return true;
+}
+
+size_t ig_lds_bytes(const IgArgs& a, int cpt, int a_rows) {
+  const size_t k_loop = 2 * (size_t)a_rows * GEMM_PITCH + 2 * GEMM_TILE_BYTES + 2 * (size_t)cpt * a.NI * a.PR * a.PW * 2;
+  const size_t staging = 64 * (size_t)IG_EPI_PITCH;
   return k_loop > staging ? k_loop : staging;
 }
 
 // Weights regrouped per output-parity class for the data gradient of a 4x4 / stride 2 / pad 1
-// convolution: Wp[b][class = 2 py + px][c][k = (o, jy, jx)] = W[b][o][c][ry + 2 jy][rx + 2 jx] with
-// ry = (py + 1) % 2 (the two taps per axis that reach pixels of that parity).
+// convolution: Wp[b][class = 2 py + px][c][k = (o, jy, jx)] = W[b][o][c][ry + 2 (1 - jy)][rx + 2 (1 - jx)]
+// with ry = (py + 1) % 2: the two taps per axis that reach pixels of that parity, in the order in
+// which the gradient rows / columns qy + py - 1 + jy they multiply ascend.
 __global__ __launch_bounds__(256) void ig_pack_class_w_kernel(const bf16_raw* __restrict__ Wt, bf16_raw* __restrict__ Wp, int Ci,
                                                               int Co, int64_t count) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -267,7 +365,7 @@ __global__ __launch_bounds__(256) void ig_pack_class_w_kernel(const bf16_raw* __
   const int py = cls >> 1, px = cls & 1;
   const int ry = (py + 1) & 1, rx = (px + 1) & 1;
   const int o = kk >> 2, jy = (kk >> 1) & 1, jx = kk & 1;
-  Wp[i] = Wt[((b * Co + o) * Ci + c) * 16 + (ry + 2 * jy) * 4 + rx + 2 * jx];
+  Wp[i] = Wt[((b * Co + o) * Ci + c) * 16 + (ry + 2 * (1 - jy)) * 4 + rx + 2 * (1 - jx)];
 }
 
 
@@ -282,8 +380,9 @@ struct IgDwArgs {
   int64_t x_img, x_model, y_img, y_model;                // element strides: sample, model
   int64_t o_model, o_split;                              // output strides: model, k split
   int Nb, Ci, Co, H, W, Ho, Wo, lgWo, lgP;
-  int NI, PR, PW, nchunk, chunk_el;
+  int NI, PR, PW, nchunk;
   int tiles_n, kt_total, kt_per_split;
+  uint32_t x_bytes, y_bytes;                             // extents of one model's slices of X and dY
 };
 
 __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
@@ -304,18 +403,21 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
 
   for (int i = t; i < patch_el / 2; i += NT) reinterpret_cast<uint32_t*>(Pt)[i] = 0u;   // margins stay zero
 
+  // Raw buffer loads, in range or at the fixed out-of-range offset (zeros): no load under control flow.
+  const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + (int64_t)b * p.x_model, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t ry = pf_rsrc(p.dY + (int64_t)b * p.y_model, p.y_bytes);
   // this thread's patch piece: channel, sample, patch row and position in the row are fixed; the image row moves with the k-tile
-  int p_row = 0, p_il = 0, p_lds = 0;
-  int64_t p_g = -1;
+  int p_row = 0, p_il = 0, p_lds = -1;
+  uint32_t p_off = PF_OOB;                                // byte offset at sample 0, image row 0
   if (t < p.nchunk) {
-    const int cpr = p.W / p.chunk_el;
+    const int cpr = p.W / 8;
     const int xc = t % cpr;
     int r = t / cpr;
     p_row = r % p.PR; r /= p.PR;
     p_il = r % p.NI;
     const int c_l = r / p.NI;
-    p_lds = ((c_l * p.NI + p_il) * p.PR + p_row) * p.PW + IG_MARGIN + xc * p.chunk_el;
-    if (c0 + c_l < p.Ci) p_g = (int64_t)b * p.x_model + (int64_t)(c0 + c_l) * HW + xc * p.chunk_el;
+    p_lds = ((c_l * p.NI + p_il) * p.PR + p_row) * p.PW + IG_MARGIN + xc * 8;
+    if (c0 + c_l < p.Ci) p_off = (uint32_t)(((int64_t)(c0 + c_l) * HW + xc * 8) * 2);
   }
   // this thread's part of the column tile: row j = t % 128, 16 consecutive k (pixels) as four groups of 4 in a row
   const int bj = t & 127, bhalf = t >> 7;
@@ -329,35 +431,28 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
       boff[g] = ((c_l * p.NI + il) * p.PR + 2 * y_l + ky) * p.PW + 2 * x + kx - 1 + IG_MARGIN;
     }
   }
-  const bf16_raw* Ab = p.dY + (int64_t)b * p.y_model;
   const int ga = t & 3, ra = t >> 2;
-  uint4 qa[2], qp;
+  uint32_t a_off[2];                                      // byte offset of the row's pixel 0 in sample 0
+#pragma unroll
+  for (int h = 0; h < 2; ++h) a_off[h] = m0 + ra + 64 * h < p.Co ? (uint32_t)((int64_t)(m0 + ra + 64 * h) * P * 2) : PF_OOB;
+  pf_u32x4 qa[2], qp;
   auto issue = [&](int kt) {
     const int kk = kt * 32 + ga * 8;                      // global pixel index of this 16-byte piece
     const int n = kk >> p.lgP, pix = kk & (P - 1);
+    const uint32_t ab = (uint32_t)n * (uint32_t)(p.y_img * 2) + (uint32_t)pix * 2u;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int m = m0 + ra + 64 * h;
-      qa[h] = (m < p.Co && n < p.Nb) ? *reinterpret_cast<const uint4*>(Ab + (int64_t)n * p.y_img + (int64_t)m * P + pix)
-                                     : make_uint4(0, 0, 0, 0);
-    }
-    qp = make_uint4(0, 0, 0, 0);
+    for (int h = 0; h < 2; ++h)
+      qa[h] = __builtin_amdgcn_raw_buffer_load_b128(ry, (int)((n < p.Nb && a_off[h] != PF_OOB) ? a_off[h] + ab : PF_OOB), 0, 0);
     const int kk0 = kt * 32;
     const int img = (kk0 >> p.lgP) + p_il;
     const int iy = 2 * ((kk0 & (P - 1)) >> p.lgWo) - 1 + p_row;
-    if (p_g >= 0 && img < p.Nb && iy >= 0 && iy < p.H) {
-      const bf16_raw* src = p.X + p_g + (int64_t)img * p.x_img + (int64_t)iy * p.W;
-      if (p.chunk_el == 8) qp = *reinterpret_cast<const uint4*>(src);
-      else { const uint2 v = *reinterpret_cast<const uint2*>(src); qp.x = v.x; qp.y = v.y; }
-    }
+    const bool ok = p_off != PF_OOB && img < p.Nb && iy >= 0 && iy < p.H;
+    qp = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(ok ? p_off + (uint32_t)img * (uint32_t)(p.x_img * 2) + (uint32_t)(iy * p.W * 2) : PF_OOB), 0, 0);
   };
   auto park = [&](int buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) *reinterpret_cast<uint4*>(As(buf) + (ra + 64 * h) * GEMM_PITCH + ga * 16) = qa[h];
-    if (t < p.nchunk) {
-      if (p.chunk_el == 8) *reinterpret_cast<uint4*>(Pt + p_lds) = qp;
-      else *reinterpret_cast<uint2*>(Pt + p_lds) = make_uint2(qp.x, qp.y);
-    }
+    for (int h = 0; h < 2; ++h) *reinterpret_cast<pf_u32x4*>(As(buf) + (ra + 64 * h) * GEMM_PITCH + ga * 16) = qa[h];
+    if (p_lds >= 0) *reinterpret_cast<pf_u32x4*>(Pt + p_lds) = qp;
   };
   auto build = [&](int buf) {
     uint32_t w[8];
@@ -381,27 +476,24 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  if (kt_begin < kt_end) {
-    issue(kt_begin);
+  // nothing below depends on the k-tile index: tiles past the end of the split are loaded (or read as
+  // zeros past the batch) and parked where nobody reads them any more
+  issue(kt_begin);
+  __syncthreads();
+  park(0);
+  issue(kt_begin + 1);
+  __syncthreads();
+  build(0);
+  __syncthreads();
+  int buf = 0;
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    park(buf ^ 1);
+    issue(kt + 2);
+    mma_tile<bf16_raw>(acc, As(buf), Cb(buf), wm, wn, lane);
     __syncthreads();
-    park(0);
+    build(buf ^ 1);
     __syncthreads();
-    build(0);
-    if (kt_begin + 1 < kt_end) issue(kt_begin + 1);
-    __syncthreads();
-    int buf = 0;
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-      const bool more = kt + 1 < kt_end;
-      if (more) park(buf ^ 1);
-      if (kt + 2 < kt_end) issue(kt + 2);
-      mma_tile<bf16_raw>(acc, As(buf), Cb(buf), wm, wn, lane);
-      __syncthreads();
-      if (more) build(buf ^ 1);
-      __syncthreads();
-      buf ^= 1;
-    }
-  } else {
-    __syncthreads();
+    buf ^= 1;
   }
   const int N = p.Ci * 16;
   float* ob = p.Out + (int64_t)blockIdx.y * p.o_split + (int64_t)b * p.o_model;
@@ -437,7 +529,7 @@ int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
                     const void* Wt, const void* bias, void* Y, int act, float slope, hipStream_t st) {
   const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
   if (kh != 4 || kw != 4 || stride != 2 || pad != 1) return HFTA_EUNSUPPORTED;
-  if (!pow2(Ho) || !pow2(Wo) || Wo < 4 || Ho * Wo < 16 || W % 4 != 0 || (128 % (Ho * Wo) != 0 && (Ho * Wo) % 128 != 0)) return HFTA_EUNSUPPORTED;
+  if (!pow2(Ho) || !pow2(Wo) || Wo < 4 || Ho * Wo < 16 || W % 8 != 0 || (128 % (Ho * Wo) != 0 && (Ho * Wo) % 128 != 0)) return HFTA_EUNSUPPORTED;
   if ((Ho * Wo >= 128 && 128 % Wo != 0) || (int64_t)Nb * Ho * Wo > 0x7fffffff) return HFTA_EUNSUPPORTED;
   if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(Wt) % 16 || reinterpret_cast<uintptr_t>(Y) % 16) return HFTA_EUNSUPPORTED;
@@ -448,11 +540,12 @@ int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
   a.o_img = (int64_t)B * Co * Ho * Wo; a.o_model = (int64_t)Co * Ho * Wo; a.o_m = (int64_t)Ho * Wo;
   a.Nb = Nb; a.Cx = Ci; a.H = H; a.W = W;
   a.M = Co; a.K = Ci * 16; a.N = Nb * Ho * Wo;
-  a.sy = 1; a.sx = 1; a.OW = Wo; a.oys = 1; a.oxs = 1;
-  ig_geometry(a, 4, 2, Ho, Wo, W);
-  const int tm = Co >= 256 ? 256 : 128;
+  if (!ig_extents(a)) return HFTA_EUNSUPPORTED;
+  a.OW = Wo; a.oys = 1; a.oxs = 1; a.tap_step = 1;
+  ig_geometry(a, 4, 2, Ho, Wo, W, 128);
+  const int tm = Co <= 64 ? 64 : 128;
   a.nchunk = 2 * a.NI * a.PR * (W / a.chunk_el);
-  if (a.nchunk > 2 * 2 * tm) return HFTA_EUNSUPPORTED;
+  if (a.nchunk > 512) return HFTA_EUNSUPPORTED;
   a.tiles_n = (a.N + 127) / 128;
   a.act = act; a.slope = slope;
   a.cls[0] = IgClass{-pad, -pad, 0, 0, 0};
@@ -461,8 +554,8 @@ int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
   const int tiles_m = (Co + tm - 1) / tm;
   if ((int64_t)tiles_m * a.tiles_n > 0x7fffffff || B > 65535) return HFTA_EUNSUPPORTED;
   dim3 grid((unsigned)(tiles_m * a.tiles_n), 1, (unsigned)B);
-  if (tm == 256) ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 256>, grid, 512, lds, st, a);
-  else ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 128>, grid, 256, lds, st, a);
+  if (tm == 64) ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 64, true>, grid, 256, lds, st, a);
+  else ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 128, true>, grid, 256, lds, st, a);
   return launch_status();
 }
 
@@ -471,7 +564,8 @@ int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
 namespace hfta {
 
 // Data gradient of the 4x4 / stride 2 / pad 1 grouped convolution (= forward of the transposed one):
-// four parity classes (grid.y), each a stride-1 2x2 correlation over dY with its regrouped weights.
+// four parity classes (grid.y = py, the two px of a tile side by side), each a stride-1 2x2 correlation
+// over dY with its regrouped weights.
 // `pack` receives the regrouped weights: conv_ig_dx_pack_bytes(...) bytes, 16-byte aligned.
 size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co) {                  // rounded up to 256 bytes
   return ((size_t)B * 4 * Ci * Co * 4 * sizeof(bf16_raw) + 255) & ~(size_t)255;
@@ -480,7 +574,7 @@ size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co) {                  // rounde
 bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad) {
   if (kh != 4 || kw != 4 || stride != 2 || pad != 1 || H % 2 || W % 2) return false;
   const int Hq = H / 2, Wq = W / 2;
-  if (!pow2(Hq) || !pow2(Wq) || Wq < 4 || Hq * Wq < 16 || (Hq * Wq >= 128 && 128 % Wq != 0)) return false;
+  if (!pow2(Hq) || !pow2(Wq) || Wq < 4 || Wq > 64 || Hq * Wq < 16) return false;
   if ((int64_t)Nb * Hq * Wq > 0x7fffffff || Ci < 32 || Co % 2 != 0) return false;
   return true;
 }
@@ -488,7 +582,7 @@ bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, 
 int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* Wt,
                const void* dY, void* dX, void* pack, hipStream_t st) {
   if (!conv_ig_dx_supported(Nb, Ci, Co, H, W, kh, kw, stride, pad)) return HFTA_EUNSUPPORTED;
-  if (reinterpret_cast<uintptr_t>(dY) % 16 || reinterpret_cast<uintptr_t>(Wt) % 16 || reinterpret_cast<uintptr_t>(dX) % 2 ||
+  if (reinterpret_cast<uintptr_t>(dY) % 16 || reinterpret_cast<uintptr_t>(Wt) % 16 || reinterpret_cast<uintptr_t>(dX) % 16 ||
       reinterpret_cast<uintptr_t>(pack) % 16 || B > 65535)
     return HFTA_EUNSUPPORTED;
   const int Hq = H / 2, Wq = W / 2;                      // class grid = the gradient's own grid (Ho x Wo)
@@ -499,27 +593,33 @@ int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   a.o_img = (int64_t)B * Ci * H * W; a.o_model = (int64_t)Ci * H * W; a.o_m = (int64_t)H * W;
   a.Nb = Nb; a.Cx = Co; a.H = Hq; a.W = Wq;
   a.M = Ci; a.K = Co * 4; a.N = Nb * Hq * Wq;
-  a.sy = -1; a.sx = -1; a.OW = W; a.oys = 2; a.oxs = 2;
-  ig_geometry(a, 2, 1, Hq, Wq, Wq);
-  const int tm = Ci >= 256 ? 256 : 128;
+  if (!ig_extents(a)) return HFTA_EUNSUPPORTED;
+  a.OW = W; a.oys = 2; a.oxs = 2; a.tap_step = 1;
+  ig_geometry(a, 2, 1, Hq, Wq, Wq, 64);
+  const int tm = Ci <= 64 ? 64 : 128;
   a.nchunk = 8 * a.NI * a.PR * (Wq / a.chunk_el);
-  if (a.nchunk > 2 * 2 * tm) return HFTA_EUNSUPPORTED;
-  a.tiles_n = (a.N + 127) / 128;
+  if (a.nchunk > 512) return HFTA_EUNSUPPORTED;
+  a.tiles_n = (a.N + 63) / 64;
   a.act = HFTA_ACT_NONE; a.slope = 0.f;
   for (int cls = 0; cls < 4; ++cls) {
     const int py = cls >> 1, px = cls & 1;
-    const int cy = py, cx = px;                           // (py + 1 - ry) / 2 with ry = (py + 1) % 2
-    a.cls[cls] = IgClass{cy, cx, py, px, (int64_t)cls * Ci * Co * 4};
+    a.cls[cls] = IgClass{py - 1, px - 1, py, px, (int64_t)cls * Ci * Co * 4};   // window rows qy + py - 1, qy + py
   }
-  const size_t lds = ig_lds_bytes(a, 8, tm);
+  const size_t lds = ig_lds_bytes(a, 8, 2 * tm);
   if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
   const int tiles_m = (Ci + tm - 1) / tm;
+  if ((int64_t)tiles_m * a.tiles_n > 0x7fffffff) return HFTA_EUNSUPPORTED;
   const int64_t count = (int64_t)B * 4 * Ci * Co * 4;
   hipLaunchKernelGGL(ig_pack_class_w_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, (const bf16_raw*)Wt,
                      (bf16_raw*)pack, Ci, Co, count);
-  dim3 grid((unsigned)(tiles_m * a.tiles_n), 4, (unsigned)B);
-  if (tm == 256) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 256>, grid, 512, lds, st, a);
-  else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128>, grid, 256, lds, st, a);
+  dim3 grid((unsigned)(tiles_m * a.tiles_n), 2, (unsigned)B);
+  if (a.chunk_el == 8) {
+    if (tm == 64) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 64, true>, grid, 256, lds, st, a);
+    else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128, true>, grid, 256, lds, st, a);
+  } else {
+    if (tm == 64) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 64, false>, grid, 256, lds, st, a);
+    else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128, false>, grid, 256, lds, st, a);
+  }
   return launch_status();
 }
 
@@ -533,7 +633,7 @@ bool conv_ig_dw_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, 
   if (kh != 4 || kw != 4 || stride != 2 || pad != 1 || H % 2 || W % 2) return false;
   const int Ho = H / 2, Wo = W / 2;
   if (!pow2(Ho) || !pow2(Wo) || Wo < 4 || Wo > 32 || Ho * Wo < 16) return false;
-  if ((int64_t)Nb * Ho * Wo > 0x7fffffff || Ci < 8 || Co < 32) return false;
+  if ((int64_t)Nb * Ho * Wo > 0x7fffffff || Co < 32) return false;   // fewer than 8 input channels: the missing columns are zeros
   return true;                                           // a k-tile's second 4x4 sample past the batch reads as zeros
 }
 
@@ -564,10 +664,12 @@ int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   a.NI = P >= 32 ? 1 : 2;
   const int TR = P >= 32 ? 32 / Wo : Ho;
   a.PR = (TR - 1) * 2 + 4;
-  a.chunk_el = W % 8 == 0 ? 8 : 4;
-  a.PW = W % 8 == 0 ? W + 16 : W + 12;
-  a.nchunk = 8 * a.NI * a.PR * (W / a.chunk_el);
-  if (a.nchunk > 256) return HFTA_EUNSUPPORTED;
+  a.PW = W + 16;
+  a.nchunk = 8 * a.NI * a.PR * (W / 8);
+  if (a.nchunk > 256 || W % 8 != 0) return HFTA_EUNSUPPORTED;
+  const int64_t xb = ((int64_t)(Nb - 1) * a.x_img + (int64_t)Ci * H * W) * 2, yb = ((int64_t)(Nb - 1) * a.y_img + (int64_t)Co * P) * 2;
+  if (xb >= ((int64_t)1 << 31) || yb >= ((int64_t)1 << 31)) return HFTA_EUNSUPPORTED;
+  a.x_bytes = (uint32_t)xb; a.y_bytes = (uint32_t)yb;
   a.tiles_n = (Ci + 7) / 8;
   a.kt_total = (int)(((int64_t)Nb * P + 31) / 32);
   const int splits = conv_ig_dw_splits(B, Nb, Ci, Co, H, W);
