@@ -17,6 +17,8 @@ using namespace hfta;
 
 namespace {
 
+constexpr int BN_UNROLL = 4;   // pieces a thread loads before it uses the first (conv layout)
+
 struct BnFwdArgs {
   const void* X; void* Y;
   const float* gamma; const float* beta;
@@ -35,12 +37,23 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
   const int chunks = p.L / VEC;
   const float shift = Elem<T>::load(x);
   float s1 = 0.f, s2 = 0.f;
-  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
-    const int n = w.n, ch = w.ch;
-    float v[VEC];
-    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
+  for (RowWalk w(chunks, NT); w.n < p.Nb;) {
+    // BN_UNROLL pieces per trip, their loads issued together (a piece past the end re-reads the
+    // channel's first piece and is not used): the bytes in flight per thread set the bandwidth
+    float v[BN_UNROLL][VEC];
+    bool ok[BN_UNROLL];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { const float d = v[e] - shift; s1 += d; s2 = fmaf(d, d, s2); }
+    for (int u = 0; u < BN_UNROLL; ++u) {
+      ok[u] = w.n < p.Nb;
+      load_vec<T, VEC>(ok[u] ? x + w.n * p.xsn + w.ch * VEC : x, v[u]);
+      w.step();
+    }
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u)
+      if (ok[u]) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { const float d = v[u][e] - shift; s1 += d; s2 = fmaf(d, d, s2); }
+      }
   }
   block_sum2<NT / 64>(s1, s2, sh);
   const float m = (float)p.Nb * (float)p.L;
@@ -60,15 +73,25 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
       p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
     }
   }
-  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
-    const int n = w.n, ch = w.ch;
-    float v[VEC];
-    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
+  for (RowWalk w(chunks, NT); w.n < p.Nb;) {
+    float v[BN_UNROLL][VEC];
+    int n[BN_UNROLL], ch[BN_UNROLL];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) v[e] = apply_act(fmaf(g, (v[e] - mean) * invstd, bt), p.act, p.slope);
-    store_vec<T, VEC>(y + n * p.ysn + ch * VEC, v);
+    for (int u = 0; u < BN_UNROLL; ++u) {
+      n[u] = w.n; ch[u] = w.ch;
+      load_vec<T, VEC>(n[u] < p.Nb ? x + n[u] * p.xsn + ch[u] * VEC : x, v[u]);
+      w.step();
+    }
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u)
+      if (n[u] < p.Nb) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[u][e] = apply_act(fmaf(g, (v[u][e] - mean) * invstd, bt), p.act, p.slope);
+        store_vec<T, VEC>(y + n[u] * p.ysn + ch[u] * VEC, v[u]);
+      }
   }
 }
+
 
 // Linear layout [.., Nb, C] (channel stride 1, the fully connected head): a workgroup owns 64
 // channels x 16 sample lanes, so the loads of a column are spread over lanes instead of walking one
@@ -139,37 +162,56 @@ __global__ __launch_bounds__(NT) void bn_bwd_conv_kernel(BnBwdArgs p) {
   const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
   const int chunks = p.L / VEC;
   float s1 = 0.f, s2 = 0.f;
-  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
-    const int n = w.n, ch = w.ch;
-    float v[VEC], d[VEC];
-    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
-    load_vec<T, VEC>(dy + n * p.dysn + ch * VEC, d);
+  for (RowWalk w(chunks, NT); w.n < p.Nb;) {
+    float v[BN_UNROLL][VEC], d[BN_UNROLL][VEC];
+    bool ok[BN_UNROLL];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const float xh = (v[e] - mean) * invstd;
-      const float gr = d[e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
-      s1 += gr;
-      s2 = fmaf(gr, xh, s2);
+    for (int u = 0; u < BN_UNROLL; ++u) {
+      ok[u] = w.n < p.Nb;
+      load_vec<T, VEC>(ok[u] ? x + w.n * p.xsn + w.ch * VEC : x, v[u]);
+      load_vec<T, VEC>(ok[u] ? dy + w.n * p.dysn + w.ch * VEC : dy, d[u]);
+      w.step();
     }
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u)
+      if (ok[u]) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float xh = (v[u][e] - mean) * invstd;
+          const float gr = d[u][e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+          s1 += gr;
+          s2 = fmaf(gr, xh, s2);
+        }
+      }
   }
   block_sum2<NT / 64>(s1, s2, sh);
   if (threadIdx.x == 0) { p.dbeta[k] = s1; p.dgamma[k] = s2; }
   const float m = (float)p.Nb * (float)p.L;
   const float mb = s1 / m, mg = s2 / m, sc = g * invstd;
   float s3 = 0.f;
-  for (RowWalk w(chunks, NT); w.n < p.Nb; w.step()) {
-    const int n = w.n, ch = w.ch;
-    float v[VEC], d[VEC];
-    load_vec<T, VEC>(x + n * p.xsn + ch * VEC, v);
-    load_vec<T, VEC>(dy + n * p.dysn + ch * VEC, d);
+  for (RowWalk w(chunks, NT); w.n < p.Nb;) {
+    float v[BN_UNROLL][VEC], d[BN_UNROLL][VEC];
+    int n[BN_UNROLL], ch[BN_UNROLL];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const float xh = (v[e] - mean) * invstd;
-      const float gr = d[e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
-      v[e] = sc * (gr - mb - xh * mg);
-      s3 += Elem<T>::to_f32(Elem<T>::from_f32(v[e]));     // the value as it is stored
+    for (int u = 0; u < BN_UNROLL; ++u) {
+      n[u] = w.n; ch[u] = w.ch;
+      const bool ok = n[u] < p.Nb;
+      load_vec<T, VEC>(ok ? x + n[u] * p.xsn + ch[u] * VEC : x, v[u]);
+      load_vec<T, VEC>(ok ? dy + n[u] * p.dysn + ch[u] * VEC : dy, d[u]);
+      w.step();
     }
-    store_vec<T, VEC>(dx + n * p.dxsn + ch * VEC, v);
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u)
+      if (n[u] < p.Nb) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float xh = (v[u][e] - mean) * invstd;
+          const float gr = d[u][e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+          v[u][e] = sc * (gr - mb - xh * mg);
+          s3 += Elem<T>::to_f32(Elem<T>::from_f32(v[u][e]));     // the value as it is stored
+        }
+        store_vec<T, VEC>(dx + n[u] * p.dxsn + ch[u] * VEC, v[u]);
+      }
   }
   if (p.dx_sum) {
     float dummy = 0.f;
