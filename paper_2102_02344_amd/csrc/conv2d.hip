@@ -17,11 +17,13 @@
 
 namespace hfta {
 int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
-                    const void* Wt, const void* bias, void* Y, int act, float slope, hipStream_t st);
+                    const void* Wt, const void* bias, void* Y, int act, float slope, void* ws, size_t ws_bytes, hipStream_t st);
+size_t conv_ig_fwd_split_bytes(int B, int Nb, int Ci, int Co, int H, int W);
+size_t conv_ig_dx_split_bytes(int B, int Nb, int Ci, int Co, int H, int W);
 size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co);
 bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad);
 int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* Wt,
-               const void* dY, void* dX, void* pack, hipStream_t st);
+               const void* dY, void* dX, void* pack, void* split_ws, hipStream_t st);
 bool conv_full_applies(int H, int W, int kh, int kw, int pad, int Ci, int Nb);
 int conv_full_fwd(int B, int Nb, int Ci, int Co, int kh, int kw, int dtype, const void* X, const void* Wt, const void* bias, void* Y,
                   int act, float slope, hipStream_t st);
@@ -855,8 +857,10 @@ size_t hfta_conv2d_grouped_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, in
   ConvGeom g;
   Lowered L;
   if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
-  if (!lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L)) return 0;
-  return L.col_bytes;
+  // the sample-folded implicit GEMM splits long reductions with few tiles over k (fp32 partial slices)
+  const size_t ig = (dtype == HFTA_BF16 && kh == 4 && kw == 4 && stride == 2 && pad == 1) ? conv_ig_fwd_split_bytes(B, Nb, Ci, Co, H, W) : 0;
+  if (!lowered_sizes(B, Nb, Ci, Co, g, kh, kw, dtype, &L)) return ig;
+  return L.col_bytes > ig ? L.col_bytes : ig;
 }
 
 int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype,
@@ -871,7 +875,8 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
     return conv_full_fwd(B, Nb, Ci, Co, kh, kw, dtype, X, Wt, bias, Y, act, act_slope, as_stream(stream));
   // bf16, 4x4 / stride 2 / pad 1, power-of-two output grids: the sample-folded implicit GEMM (no workspace)
   if (dtype == HFTA_BF16) {
-    rc = conv_ig_forward(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, X, Wt, bias, Y, act, act_slope, as_stream(stream));
+    rc = conv_ig_forward(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, X, Wt, bias, Y, act, act_slope, workspace, ws_bytes,
+                         as_stream(stream));
     if (rc != HFTA_EUNSUPPORTED) return rc;
   }
   Lowered L;
@@ -931,7 +936,8 @@ size_t hfta_conv2d_grouped_bwd_min_workspace_bytes(int B, int Nb, int Ci, int Co
   if (check_conv(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, &g) != HFTA_OK) return 0;
   const size_t imp = implicit_bwd_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype, g);
   const size_t pk = ig_dx_applies(Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype) ? conv_ig_dx_pack_bytes(B, Ci, Co) : 0;
-  return pk ? align256(imp) + pk : imp;                 // regrouped weights of the data gradient behind the partials
+  // behind the weight gradient's partials: the data gradient's k-split slices, then its regrouped weights
+  return pk ? align256(imp) + align256(conv_ig_dx_split_bytes(B, Nb, Ci, Co, H, W)) + pk : imp;
 }
 
 /* The size that enables the column-buffer path; anything from the implicit path's own need (the
@@ -946,7 +952,8 @@ size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, in
   const size_t low = L.dcol_bytes + L.dyp_bytes + L.part_bytes;
   const size_t base = low > imp ? low : imp;
   const size_t pk = dx_pack_bytes(B, Ci, Co, kh, kw, stride, dtype, g);
-  return pk ? align256(base) + pk : base;      // regrouped weights behind everything else
+  const size_t dxs = ig_dx_applies(Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype) ? align256(conv_ig_dx_split_bytes(B, Nb, Ci, Co, H, W)) : 0;
+  return pk ? align256(base) + dxs + pk : base;      // (k-split slices and) regrouped weights behind everything else
 }
 
 int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, int dtype,
@@ -978,7 +985,9 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
     const size_t need = hfta_conv2d_grouped_bwd_min_workspace_bytes(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, dtype);
     const size_t end = ws_bytes & ~(size_t)255;
     if (ws_bytes >= need && end >= pk && reinterpret_cast<uintptr_t>(workspace) % 256 == 0) {
-      rc = conv_ig_dx(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, Wt, dY, dX, reinterpret_cast<unsigned char*>(workspace) + end - pk, st);
+      const size_t dxs = align256(conv_ig_dx_split_bytes(B, Nb, Ci, Co, H, W));
+      unsigned char* wend = reinterpret_cast<unsigned char*>(workspace) + end;
+      rc = conv_ig_dx(B, Nb, Ci, Co, H, W, kh, kw, stride, pad, Wt, dY, dX, wend - pk, dxs ? wend - pk - dxs : nullptr, st);
       if (rc == HFTA_OK) dX = nullptr;
       else if (rc != HFTA_EUNSUPPORTED) return rc;
     }

@@ -26,6 +26,22 @@ namespace {
 
 constexpr int IG_MARGIN = 8;            // zero columns left of a patch row (keeps the data 16-byte aligned)
 
+// Workgroups are dispatched to the 8 XCDs (each with its own L2) round-robin by their linear id.
+// The kernels are launched on a 1-D grid and turn the id into a logical (x, y, z) block such that
+// consecutive logical blocks -- the column tiles that share a weight slab, then the row tiles that
+// share a patch -- run on the SAME XCD at about the same time, instead of each XCD fetching every
+// slab for itself (the 8x8 layer's forward went from a 32 % L2 hit rate to sharing).
+struct IgGrid { int gx, gy, gz; };
+__device__ __forceinline__ void ig_block(const IgGrid& g, int& bx, int& by, int& bz) {
+  const int total = g.gx * g.gy * g.gz, id = blockIdx.x;
+  int logical = id;
+  if (total % 8 == 0) logical = (id & 7) * (total >> 3) + (id >> 3);
+  bx = logical % g.gx;
+  const int r = logical / g.gx;
+  by = r % g.gy;
+  bz = r / g.gy;
+}
+
 struct IgClass {
   int oy, ox;                           // patch row / column of tap (0, 0) for output (0, 0), before the margin
   int out_y0, out_x0;                   // where the class's outputs start in the output image
@@ -42,9 +58,12 @@ struct IgArgs {
   int Ho, Wo, lgWo, lgP;                // logical output grid per sample (powers of two)
   int OW, oys, oxs;                     // output image width in memory, output step per grid step
   int tap_step;                         // 1 (patch elements between the taps of a window row; see the column-tile build)
-  int NI, TR, PR, PW;                   // samples per tile, grid rows per tile and sample, patch rows, patch pitch
+  int NI, TR, PR, PW, SP;               // samples per tile, grid rows per tile and sample, patch rows, row pitch, sample pitch (elements)
   int nchunk, chunk_el;                 // 16- or 8-byte pieces of patch rows per k-tile, elements per piece
   uint32_t x_bytes, a_bytes;            // extent of one model's slice of the view operand / of its weights
+  IgGrid grid;                          // logical grid: x = tiles, y = class / k split, z = model
+  int ksplit, kt_per_split;             // k range split over the grid's y (> 1: fp32 partial slices instead of Out)
+  float* part; int64_t part_split;      // partial slices [split][same indexing as Out]
   int tiles_n, act;
   float slope;
   IgClass cls[4];
@@ -77,7 +96,7 @@ __device__ __forceinline__ void ig_stage64(f32x16_t (&acc)[2][FN], unsigned char
 // Four wavefronts; each computes 64 rows x 64 columns of a TM = 128 row tile, or 64 rows x 32 columns
 // of a TM = 64 row tile (layers with at most 64 output rows).
 // PAIR (data gradient): the tile's 128 columns are 64 pixels of the parity class px = 0 followed by
-// the same 64 pixels of px = 1 (blockIdx.y = py); the weight tile holds both classes' rows, a
+// the same 64 pixels of px = 1 (the grid's y = py); the weight tile holds both classes' rows, a
 // wavefront works on the class its columns belong to, and the epilogue interleaves the two classes
 // into whole 16-byte pieces of the output rows.
 //
@@ -108,14 +127,18 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   auto As = [&](int buf) { return smem + buf * A_BYTES; };
   auto Cb = [&](int buf) { return smem + 2 * A_BYTES + buf * GEMM_TILE_BYTES; };
-  const int chan_el = p.NI * p.PR * p.PW;
+  const int chan_el = p.NI * p.SP;
   const int patch_el = CPT * chan_el;
   auto Pt = [&](int buf) { return reinterpret_cast<bf16_raw*>(smem + 2 * A_BYTES + 2 * GEMM_TILE_BYTES) + buf * patch_el; };
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  int bx, by, b;
+  ig_block(p.grid, bx, by, b);
+  const int tile_m = bx / p.tiles_n, tile_n = bx % p.tiles_n;
   const int m0 = tile_m * TM, n0 = tile_n * COLS;
-  const IgClass cl0 = p.cls[PAIR ? 2 * blockIdx.y : 0];
-  const int b = blockIdx.z;
+  // grid y: PAIR py + 2 * (k split), else the k split
+  const int py2 = PAIR ? 2 * (by & 1) : 0;
+  const int split = PAIR ? by >> 1 : by;
+  const IgClass cl0 = p.cls[py2];
   const int P = 1 << p.lgP;
   const int img0 = n0 >> p.lgP;                          // first sample of the tile
   const int y0 = (n0 & (P - 1)) >> p.lgWo;               // first grid row (tiles inside one sample)
@@ -123,6 +146,7 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
   const int rmin = cl0.oy;                               // first patch row's image row for grid row 0 (the same for both classes of a pair)
   const int row_base = y0 * S + rmin;
   const int ktiles = (p.K + 31) / 32;
+  const int kt0 = split * p.kt_per_split, kt1 = min(ktiles, kt0 + p.kt_per_split);
 
   // position of the wavefront's block of the tile
   const int wm = TM == 128 ? wave >> 1 : 0;
@@ -147,7 +171,7 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
       const int il = r % p.NI, c_l = r / p.NI;
       const int iy = row_base + pr, img = img0 + il;
       pcl[i] = c_l;
-      pl[i] = ((c_l * p.NI + il) * p.PR + pr) * p.PW + IG_MARGIN + xc * CH;
+      pl[i] = (c_l * p.NI + il) * p.SP + pr * p.PW + IG_MARGIN + xc * CH;
       if (iy >= 0 && iy < p.H && img < p.Nb)
         pxo[i] = (uint32_t)(((int64_t)img * p.x_img + (int64_t)c_l * HW + (int64_t)iy * p.W + xc * CH) * 2);
     }
@@ -157,11 +181,11 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
   const int bcol = t & 127, bhalf = t >> 7;
   int boff;                                               // patch element of tap (0, 0), first channel of this half
   {
-    const IgClass cl = PAIR ? p.cls[2 * blockIdx.y + (bcol >> 6)] : cl0;
+    const IgClass cl = PAIR ? p.cls[py2 + (bcol >> 6)] : cl0;
     const int n = n0 + (PAIR ? (bcol & 63) : bcol);
     const int il = (n >> p.lgP) - img0;
     const int y = (n & (P - 1)) >> p.lgWo, x = n & (p.Wo - 1);
-    boff = (il * p.PR + (y - y0) * S + (cl.oy - rmin)) * p.PW + x * S + cl.ox + IG_MARGIN;
+    boff = il * p.SP + ((y - y0) * S + (cl.oy - rmin)) * p.PW + x * S + cl.ox + IG_MARGIN;
     boff += ((bhalf * KPT) / TK) * chan_el;
   }
   // ---- weight pieces: rows ra + 64 h of the weight tile, 8 k at ga
@@ -171,7 +195,7 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
   for (int h = 0; h < NA; ++h) {
     const int r = ra + (NT / 4) * h;                      // PAIR: first TM rows class px = 0, then class px = 1
     const int m = m0 + r % TM;
-    const int64_t a_off = PAIR ? p.cls[2 * blockIdx.y + r / TM].a_off : cl0.a_off;
+    const int64_t a_off = PAIR ? p.cls[py2 + r / TM].a_off : cl0.a_off;
     wo[h] = m < p.M ? (uint32_t)((a_off + (int64_t)m * p.K + ga * 8) * 2) : PF_OOB;
   }
   pf_u32x4 qa[NA], qp[2];
@@ -253,23 +277,23 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
     }
   };
 
-  issue_a(0);
-  issue_p(0);
+  issue_a(kt0);
+  issue_p(kt0);
   // zero both patch buffers once: the margins stay zero
   for (int i = t; i < 2 * patch_el / 2; i += NT) reinterpret_cast<uint32_t*>(Pt(0))[i] = 0u;
   __syncthreads();
   park_a(0);
   park_p(0);
-  issue_a(1);
-  issue_p(1);
+  issue_a(kt0 + 1);
+  issue_p(kt0 + 1);
   __syncthreads();
   build_read(0);
   park_p(1);
-  issue_p(2);
+  issue_p(kt0 + 2);
   build_write(0);
   __syncthreads();
-  for (int kt = 0; kt < ktiles; ++kt) {
-    const int buf = kt & 1;
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const int buf = (kt - kt0) & 1;
     build_read(buf ^ 1);                                  // gather of column tile kt + 1 (patch kt + 1 was parked an iteration ago)
     park_a(buf ^ 1);                                      // weights kt + 1
     park_p(buf);                                          // patch kt + 2
@@ -278,6 +302,52 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
     mma(buf);
     build_write(buf ^ 1);
     __syncthreads();
+  }
+
+  if (p.ksplit > 1) {
+    // ---- split k: this workgroup's fp32 partial tile goes to its slice, indexed like the output;
+    // bias, activation and the conversion happen in ig_split_finish_kernel
+    float* lds_f = reinterpret_cast<float*>(smem);
+    float* ob = p.part + (int64_t)split * p.part_split + (int64_t)b * p.o_model;
+    constexpr int FP = 132;                               // floats per staged row
+#pragma unroll 1
+    for (int pass = 0; pass < TM / 64; ++pass) {
+      const int mp = m0 + 64 * pass;
+      if (wm == pass) {
+        const int ml = lane & 31, nq = (lane >> 5) * 4;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              *reinterpret_cast<float4*>(lds_f + (i * 32 + ml) * FP + col0 + j * 32 + 8 * q + nq) =
+                  make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int id = t; id < 64 * 32; id += NT) {
+        const int rr = id >> 5, pc = id & 31;
+        const int m = mp + rr;
+        if (!PAIR) {
+          const int n = n0 + pc * 4;
+          if (m >= p.M || n >= p.N) continue;
+          const int img = n >> p.lgP, pix = n & (P - 1);
+          *reinterpret_cast<float4*>(ob + (int64_t)img * p.o_img + (int64_t)m * p.o_m + pix) =
+              *reinterpret_cast<const float4*>(lds_f + rr * FP + pc * 4);
+        } else {
+          const int n = n0 + pc * 2;                      // 2 pixels x 2 classes = 4 consecutive output elements
+          if (m >= p.M || n >= p.N) continue;
+          const int img = n >> p.lgP, y = (n & (P - 1)) >> p.lgWo, x = n & (p.Wo - 1);
+          const float2 e = *reinterpret_cast<const float2*>(lds_f + rr * FP + pc * 2);
+          const float2 o = *reinterpret_cast<const float2*>(lds_f + rr * FP + 64 + pc * 2);
+          *reinterpret_cast<float4*>(ob + (int64_t)img * p.o_img + (int64_t)m * p.o_m + (int64_t)(y * p.oys + cl0.out_y0) * p.OW + x * p.oxs) =
+              make_float4(e.x, o.x, e.y, o.y);
+        }
+      }
+      if (pass + 1 < TM / 64) __syncthreads();
+    }
+    return;
   }
 
   // ---- epilogue: bias + activation, 64 rows at a time through an LDS staging tile, then whole
@@ -324,6 +394,7 @@ int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 // patch geometry shared by the host-side checks and the launch
+// patch geometry shared by the host-side checks and the launch
 bool ig_geometry(IgArgs& a, int KH, int S, int Ho, int Wo, int W, int cols) {
   a.Ho = Ho; a.Wo = Wo; a.lgWo = ilog2(Wo); a.lgP = ilog2(Ho * Wo);
   const int P = Ho * Wo;
@@ -331,6 +402,7 @@ bool ig_geometry(IgArgs& a, int KH, int S, int Ho, int Wo, int W, int cols) {
   a.PR = (a.TR - 1) * S + KH;
   a.chunk_el = W % 8 == 0 ? 8 : 4;
   a.PW = W % 8 == 0 ? W + 16 : W + 12;
+  a.SP = a.PR * a.PW;
   return true;
 }
 
@@ -343,8 +415,8 @@ bool ig_extents(IgArgs& a) {
 }
 
 size_t ig_lds_bytes(const IgArgs& a, int cpt, int a_rows) {
-  const size_t k_loop = 2 * (size_t)a_rows * GEMM_PITCH + 2 * GEMM_TILE_BYTES + 2 * (size_t)cpt * a.NI * a.PR * a.PW * 2;
-  const size_t staging = 64 * (size_t)IG_EPI_PITCH;
+  const size_t k_loop = 2 * (size_t)a_rows * GEMM_PITCH + 2 * GEMM_TILE_BYTES + 2 * (size_t)cpt * a.NI * a.SP * 2;
+  const size_t staging = a.ksplit > 1 ? 64 * (size_t)132 * 4 : 64 * (size_t)IG_EPI_PITCH;
   return k_loop > staging ? k_loop : staging;
 }
 
@@ -374,7 +446,7 @@ __global__ __launch_bounds__(256) void ig_pack_class_w_kernel(const bf16_raw* __
 // Rows are output channels (dY is k-contiguous inside a sample), columns the 128 taps of 8 input
 // channels, and a k-tile is 32 consecutive output pixels (of one sample, or of two 4x4 samples).
 // The column tile [128 j][32 k] is built from the patch of the 8 channels' input rows those pixels
-// touch.  blockIdx.y splits the k range; partial sums go to fp32 slices reduced afterwards.
+// touch.  The grid's y splits the k range; partial sums go to fp32 slices reduced afterwards.
 struct IgDwArgs {
   const bf16_raw* X; const bf16_raw* dY; float* Out;
   int64_t x_img, x_model, y_img, y_model;                // element strides: sample, model
@@ -382,6 +454,7 @@ struct IgDwArgs {
   int Nb, Ci, Co, H, W, Ho, Wo, lgWo, lgP;
   int NI, PR, PW, nchunk;
   int tiles_n, kt_total, kt_per_split;
+  IgGrid grid;                                           // logical grid: x = tiles, y = k split, z = model
   uint32_t x_bytes, y_bytes;                             // extents of one model's slices of X and dY
 };
 
@@ -394,11 +467,12 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
   const int chan_el = p.NI * p.PR * p.PW, patch_el = 8 * chan_el;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  int bx, by, b;
+  ig_block(p.grid, bx, by, b);
+  const int tile_m = bx / p.tiles_n, tile_n = bx % p.tiles_n;
   const int m0 = tile_m * 128, c0 = tile_n * 8;
-  const int b = blockIdx.z;
   const int P = 1 << p.lgP, HW = p.H * p.W;
-  const int kt_begin = blockIdx.y * p.kt_per_split;
+  const int kt_begin = by * p.kt_per_split;
   const int kt_end = min(p.kt_total, kt_begin + p.kt_per_split);
 
   for (int i = t; i < patch_el / 2; i += NT) reinterpret_cast<uint32_t*>(Pt)[i] = 0u;   // margins stay zero
@@ -496,8 +570,38 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
     buf ^= 1;
   }
   const int N = p.Ci * 16;
-  float* ob = p.Out + (int64_t)blockIdx.y * p.o_split + (int64_t)b * p.o_model;
+  float* ob = p.Out + (int64_t)by * p.o_split + (int64_t)b * p.o_model;
   store_tile<float, float, false>(acc, smem, ob, N, p.Co, N, m0, c0 * 16, (const float*)nullptr, 0, HFTA_ACT_NONE, 0.f, 16, t);
+}
+
+// out[i] = bf16(act(sum of the k splits' partials + bias of i's channel)); 8 consecutive elements per thread
+__global__ __launch_bounds__(256) void ig_split_finish_kernel(const float* __restrict__ part, bf16_raw* __restrict__ out,
+                                                              const bf16_raw* __restrict__ bias, int64_t count8, int64_t slice,
+                                                              int splits, int64_t o_m, int channels, int act, float slope) {
+  const int64_t i8 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i8 >= count8) return;
+  const int64_t i = i8 * 8;
+  float v[8];
+  {
+    const float4 a = *reinterpret_cast<const float4*>(part + i), c = *reinterpret_cast<const float4*>(part + i + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
+  }
+  for (int s = 1; s < splits; ++s) {
+    const float4 a = *reinterpret_cast<const float4*>(part + s * slice + i), c = *reinterpret_cast<const float4*>(part + s * slice + i + 4);
+    v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w; v[4] += c.x; v[5] += c.y; v[6] += c.z; v[7] += c.w;
+  }
+  const float bm = bias ? bf16_to_f32(bias[(i / o_m) % channels]) : 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = cheap_act(v[e] + bm, act, slope);
+  *reinterpret_cast<uint4*>(out + i) = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+}
+
+// k split of the forward kernel: taken when the tiles alone leave most compute units with a single
+// workgroup and the reduction is long (the 8x8 layers: 320 tiles, 128 k-tiles: 101 -> 90 us).  With
+// 640 tiles and more, and for the class-pair data gradient, the split measured no gain or a loss.
+int ig_pick_ksplit(int64_t blocks, int ktiles, bool pair) {
+  if (pair || blocks >= 384 || ktiles < 64) return 1;
+  return ktiles >= 128 ? 4 : 2;
 }
 
 __global__ __launch_bounds__(256) void ig_split_reduce_kernel(const float4* __restrict__ partial, float4* __restrict__ out, int64_t count4, int splits) {
@@ -516,17 +620,28 @@ constexpr size_t IG_MAX_LDS = 96 * 1024;
 // Kernels here take more dynamic LDS than the default limit allows: the limit of each instantiation
 // is raised before its launches (an idempotent attribute of the loaded kernel, not library state).
 template <typename K>
-void ig_launch(K kernel, dim3 grid, int threads, size_t lds, hipStream_t st, const IgArgs& a) {
+void ig_launch(K kernel, dim3 grid, int threads, size_t lds, hipStream_t st, IgArgs a) {
   if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)IG_MAX_LDS);
-  hipLaunchKernelGGL(kernel, grid, dim3((unsigned)threads), lds, st, a);
+  a.grid = IgGrid{(int)grid.x, (int)grid.y, (int)grid.z};
+  hipLaunchKernelGGL(kernel, dim3(grid.x * grid.y * grid.z), dim3((unsigned)threads), lds, st, a);
 }
 
 }  // namespace
 
 // Forward of the grouped convolution (also the data gradient of the transposed convolution).
 // HFTA_EUNSUPPORTED when the shape is outside what the kernel handles (the caller falls back).
+// fp32 partial slices the forward wants for its k split (0: no split).  Without that much workspace it runs unsplit.
+size_t conv_ig_fwd_split_bytes(int B, int Nb, int Ci, int Co, int H, int W) {
+  const int Ho = H / 2, Wo = W / 2, tm = Co <= 64 ? 64 : 128;
+  if (Ho <= 0 || Wo <= 0) return 0;
+  const int64_t blocks = (int64_t)((Co + tm - 1) / tm) * (((int64_t)Nb * Ho * Wo + 127) / 128) * B;
+  const int ks = ig_pick_ksplit(blocks, (Ci * 16 + 31) / 32, false);
+  return ks > 1 ? (size_t)ks * Nb * B * Co * Ho * Wo * sizeof(float) : 0;
+}
+
 int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
-                    const void* Wt, const void* bias, void* Y, int act, float slope, hipStream_t st) {
+                    const void* Wt, const void* bias, void* Y, int act, float slope, void* ws, size_t ws_bytes,
+                    hipStream_t st) {
   const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
   if (kh != 4 || kw != 4 || stride != 2 || pad != 1) return HFTA_EUNSUPPORTED;
   if (!pow2(Ho) || !pow2(Wo) || Wo < 4 || Ho * Wo < 16 || W % 8 != 0 || (128 % (Ho * Wo) != 0 && (Ho * Wo) % 128 != 0)) return HFTA_EUNSUPPORTED;
@@ -553,9 +668,22 @@ int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
   if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
   const int tiles_m = (Co + tm - 1) / tm;
   if ((int64_t)tiles_m * a.tiles_n > 0x7fffffff || B > 65535) return HFTA_EUNSUPPORTED;
-  dim3 grid((unsigned)(tiles_m * a.tiles_n), 1, (unsigned)B);
-  if (tm == 64) ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 64, true>, grid, 256, lds, st, a);
-  else ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 128, true>, grid, 256, lds, st, a);
+  const int ktiles = (a.K + 31) / 32;
+  const size_t need = conv_ig_fwd_split_bytes(B, Nb, Ci, Co, H, W);
+  a.ksplit = (need && ws && ws_bytes >= need && reinterpret_cast<uintptr_t>(ws) % 16 == 0) ? ig_pick_ksplit((int64_t)tiles_m * a.tiles_n * B, ktiles, false) : 1;
+  a.kt_per_split = (ktiles + a.ksplit - 1) / a.ksplit;
+  a.part = reinterpret_cast<float*>(ws);
+  a.part_split = (int64_t)Nb * a.o_img;
+  const size_t lds2 = ig_lds_bytes(a, 2, tm);
+  dim3 grid((unsigned)(tiles_m * a.tiles_n), (unsigned)a.ksplit, (unsigned)B);
+  if (tm == 64) ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 64, true>, grid, 256, lds2, st, a);
+  else ig_launch(conv_ig_fwd_kernel<4, 4, 2, false, 128, true>, grid, 256, lds2, st, a);
+  if (a.ksplit > 1) {
+    if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+    const int64_t count8 = a.part_split / 8;
+    hipLaunchKernelGGL(ig_split_finish_kernel, dim3((unsigned)((count8 + 255) / 256)), dim3(256), 0, st, (const float*)a.part,
+                       a.Out, a.bias, count8, a.part_split, a.ksplit, a.o_m, B * Co, act, slope);
+  }
   return launch_status();
 }
 
@@ -579,8 +707,17 @@ bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, 
   return true;
 }
 
+// fp32 partial slices the data gradient wants for its k split (0: no split)
+size_t conv_ig_dx_split_bytes(int B, int Nb, int Ci, int Co, int H, int W) {
+  const int Hq = H / 2, Wq = W / 2, tm = Ci <= 64 ? 64 : 128;
+  if (Hq <= 0 || Wq <= 0) return 0;
+  const int64_t blocks = (int64_t)((Ci + tm - 1) / tm) * (((int64_t)Nb * Hq * Wq + 63) / 64) * 2 * B;
+  const int ks = ig_pick_ksplit(blocks, (Co * 4 + 31) / 32, true);
+  return ks > 1 ? (size_t)ks * Nb * B * Ci * H * W * sizeof(float) : 0;
+}
+
 int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* Wt,
-               const void* dY, void* dX, void* pack, hipStream_t st) {
+               const void* dY, void* dX, void* pack, void* split_ws, hipStream_t st) {
   if (!conv_ig_dx_supported(Nb, Ci, Co, H, W, kh, kw, stride, pad)) return HFTA_EUNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(dY) % 16 || reinterpret_cast<uintptr_t>(Wt) % 16 || reinterpret_cast<uintptr_t>(dX) % 16 ||
       reinterpret_cast<uintptr_t>(pack) % 16 || B > 65535)
@@ -612,13 +749,26 @@ int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   const int64_t count = (int64_t)B * 4 * Ci * Co * 4;
   hipLaunchKernelGGL(ig_pack_class_w_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, (const bf16_raw*)Wt,
                      (bf16_raw*)pack, Ci, Co, count);
-  dim3 grid((unsigned)(tiles_m * a.tiles_n), 2, (unsigned)B);
+  const int ktiles = (a.K + 31) / 32;
+  a.ksplit = (split_ws && reinterpret_cast<uintptr_t>(split_ws) % 16 == 0) ? ig_pick_ksplit((int64_t)tiles_m * a.tiles_n * 2 * B, ktiles, true) : 1;
+  a.kt_per_split = (ktiles + a.ksplit - 1) / a.ksplit;
+  a.part = reinterpret_cast<float*>(split_ws);
+  a.part_split = (int64_t)Nb * a.o_img;
+  const size_t lds2 = ig_lds_bytes(a, 8, 2 * tm);
+  if (lds2 > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
+  dim3 grid((unsigned)(tiles_m * a.tiles_n), (unsigned)(2 * a.ksplit), (unsigned)B);
   if (a.chunk_el == 8) {
-    if (tm == 64) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 64, true>, grid, 256, lds, st, a);
-    else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128, true>, grid, 256, lds, st, a);
+    if (tm == 64) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 64, true>, grid, 256, lds2, st, a);
+    else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128, true>, grid, 256, lds2, st, a);
   } else {
-    if (tm == 64) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 64, false>, grid, 256, lds, st, a);
-    else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128, false>, grid, 256, lds, st, a);
+    if (tm == 64) ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 64, false>, grid, 256, lds2, st, a);
+    else ig_launch(conv_ig_fwd_kernel<2, 2, 1, true, 128, false>, grid, 256, lds2, st, a);
+  }
+  if (a.ksplit > 1) {
+    if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
+    const int64_t count8 = a.part_split / 8;
+    hipLaunchKernelGGL(ig_split_finish_kernel, dim3((unsigned)((count8 + 255) / 256)), dim3(256), 0, st, (const float*)a.part,
+                       a.Out, (const bf16_raw*)nullptr, count8, a.part_split, a.ksplit, a.o_m, B * Ci, HFTA_ACT_NONE, 0.f);
   }
   return launch_status();
 }
@@ -684,7 +834,9 @@ int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   const int tiles_m = (Co + 127) / 128;
   if (lds > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_ig_dw_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)IG_MAX_LDS);
-  hipLaunchKernelGGL(conv_ig_dw_kernel, dim3((unsigned)(tiles_m * a.tiles_n), (unsigned)splits, (unsigned)B), dim3(256), lds, st, a);
+  a.grid = IgGrid{tiles_m * a.tiles_n, splits, B};
+  if ((int64_t)a.grid.gx * splits * B > 0x7fffffff) return HFTA_EUNSUPPORTED;
+  hipLaunchKernelGGL(conv_ig_dw_kernel, dim3((unsigned)(a.grid.gx * splits * B)), dim3(256), lds, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   if (splits > 1) {
     const int64_t count4 = (int64_t)B * a.o_model / 4;

@@ -570,9 +570,10 @@ CONV_CASES = [
     (1, 2, 32, 9, 32, 4, 2, 1),     # the same with K = 36: weights gathered tap by tap
     (2, 5, 32, 100, 4, 4, 1, 0),    # generator's first layer seen as a convolution: whole-image window, batched-GEMM path
     (2, 3, 5, 3, 3, 3, 1, 0),       # whole-image window with K = 45 (no 16-byte pieces)
-    (2, 3, 264, 40, 8, 4, 2, 1),    # 4x4 outputs: 8 samples per column tile, ragged sample tail; 256-row data-gradient tiles
+    (2, 3, 264, 40, 8, 4, 2, 1),    # 4x4 outputs: 8 samples per column tile, ragged sample tail; forward reduction (K = 4224) split four ways
     (1, 5, 40, 48, 8, 4, 2, 1),     # weight gradient with two 4x4 samples per k-tile and an odd number of samples
-    (1, 3, 16, 300, 16, 4, 2, 1),   # forward on 256-row tiles, two 8x8 samples per column tile, ragged rows and samples
+    (1, 3, 16, 300, 16, 4, 2, 1),   # forward on 128-row tiles, two 8x8 samples per column tile, ragged rows and samples
+    (1, 2, 32, 512, 8, 4, 2, 1),    # data gradient with a long reduction (K = 2048) on 64-row class-pair tiles
 ]
 
 
