@@ -144,6 +144,8 @@ def kernel_label(name, a):
         if a[14] is not None:                  # dX and dW are asked for in separate calls
             if full:
                 return small % "dx"
+            if dt == 1 and (kh, kw, stride, pad) == (4, 4, 2, 1) and Ci <= 4:
+                return "conv_dx_fewc_kernel"
             return ("ig_pack_class_w_kernel + conv_ig_fwd_kernel<2,2,1,pair>" if ig and Ci >= 32
                     else "conv2d dX: pack_dy_kernel + gemm + col2im_lds_kernel")
         if full:

@@ -29,6 +29,8 @@ int conv_full_fwd(int B, int Nb, int Ci, int Co, int kh, int kw, int dtype, cons
                   int act, float slope, hipStream_t st);
 int conv_full_dx(int B, int Nb, int Ci, int Co, int kh, int kw, int dtype, const void* Wt, const void* dY, void* dX, hipStream_t st);
 int conv_full_dw(int B, int Nb, int Ci, int Co, int kh, int kw, int dtype, const void* X, const void* dY, float* dW, hipStream_t st);
+bool conv_dx_fewc_supported(int Nb, int B, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad);
+int conv_dx_fewc(int B, int Nb, int Ci, int Co, int H, int W, const void* Wt, const void* dY, void* dX, hipStream_t st);
 bool conv_ig_dw_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad);
 int conv_ig_dw_splits(int B, int Nb, int Ci, int Co, int H, int W);
 int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad, const void* X,
@@ -976,6 +978,12 @@ int hfta_conv2d_grouped_bwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
       if (rc != HFTA_OK) return rc;
       dW = nullptr;
     }
+  }
+  // at most 4 input channels: direct vector arithmetic (a matrix tile would be 95 % empty)
+  if (dX && dtype == HFTA_BF16 && conv_dx_fewc_supported(Nb, B, Ci, Co, H, W, kh, kw, stride, pad)) {
+    rc = conv_dx_fewc(B, Nb, Ci, Co, H, W, Wt, dY, dX, st);
+    if (rc == HFTA_OK) dX = nullptr;
+    else if (rc != HFTA_EUNSUPPORTED) return rc;
   }
   // Data gradient as an implicit GEMM over (sample, pixel) columns per parity class: its regrouped
   // weights take the last bytes of the workspace (every other user starts at its front, and both the

@@ -574,6 +574,8 @@ CONV_CASES = [
     (1, 5, 40, 48, 8, 4, 2, 1),     # weight gradient with two 4x4 samples per k-tile and an odd number of samples
     (1, 3, 16, 300, 16, 4, 2, 1),   # forward on 128-row tiles, two 8x8 samples per column tile, ragged rows and samples
     (1, 2, 32, 512, 8, 4, 2, 1),    # data gradient with a long reduction (K = 2048) on 64-row class-pair tiles
+    (2, 2, 3, 20, 80, 4, 2, 1),     # few-channel data gradient: 40x40 q grid (ragged 32x8 tiles), Co not a multiple of 8
+    (1, 3, 1, 9, 12, 4, 2, 1),      # the same with one channel and a q grid smaller than a tile
 ]
 
 
