@@ -18,6 +18,8 @@
 //   weight gradient: conv_ig_dw_kernel below, dW[o][(c, ky, kx)] = sum_{(n, y, x)} dY[n][o][y][x] X[n][c][...].
 //
 // bf16 only; output grids whose width and height are powers of two; see ig_*_supported.
+#include <mutex>
+#include <vector>
 #include "gemm_pf.h"
 
 namespace hfta {
@@ -394,15 +396,58 @@ int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 // patch geometry shared by the host-side checks and the launch
-// patch geometry shared by the host-side checks and the launch
-bool ig_geometry(IgArgs& a, int KH, int S, int Ho, int Wo, int W, int cols) {
+// Patch geometry.  The gather reads 2-byte elements: the LDS serves 32 lanes per clock from 32
+// banks of 4 bytes (lanes on the same word are served together; measured: 2 clocks for a
+// conflict-free 64-lane read, 2n for an n-way conflict), and the 32 lanes of a half wavefront are 32
+// consecutive columns, i.e. several image rows (and samples) of small images.  With the natural row
+// pitch the four rows of an 8x8 layer that a half wavefront touches fall on the same banks (4-way,
+// 8 clocks per read).  Row pitch and sample pitch are therefore searched (multiples of 8 elements,
+// so that 16-byte pieces stay aligned) for the fewest conflicts over all taps of a window row.
+// (The search is a pure function of the layer geometry; its results are memoised, a call costs the
+// host ~100 us otherwise.)
+struct IgPitchKey { int KW, S, Ho, Wo, W, cols, pair, PW, SP; };
+std::mutex ig_pitch_mutex;
+std::vector<IgPitchKey> ig_pitch_cache;
+
+bool ig_geometry(IgArgs& a, int KW, int KH, int S, int Ho, int Wo, int W, int cols, bool pair) {
   a.Ho = Ho; a.Wo = Wo; a.lgWo = ilog2(Wo); a.lgP = ilog2(Ho * Wo);
   const int P = Ho * Wo;
   if (P >= cols) { a.NI = 1; a.TR = cols / Wo; } else { a.NI = cols / P; a.TR = Ho; }
   a.PR = (a.TR - 1) * S + KH;
   a.chunk_el = W % 8 == 0 ? 8 : 4;
-  a.PW = W % 8 == 0 ? W + 16 : W + 12;
-  a.SP = a.PR * a.PW;
+  const int pw0 = W % 8 == 0 ? W + 16 : W + 12;
+  {
+    std::lock_guard<std::mutex> lock(ig_pitch_mutex);
+    for (const IgPitchKey& k : ig_pitch_cache)
+      if (k.KW == KW && k.S == S && k.Ho == Ho && k.Wo == Wo && k.W == W && k.cols == cols && k.pair == (int)pair) {
+        a.PW = k.PW; a.SP = k.SP;
+        return true;
+      }
+  }
+  const int floor_cost = (pair ? 2 : 1) * KW * (cols / 32);   // one pass per half wavefront and tap
+  int64_t best = -1;
+  for (int i = 0; i < 6 && best / (1 << 20) != floor_cost; ++i)
+    for (int j = 0; j < 8 && best / (1 << 20) != floor_cost; ++j) {
+      const int pw = pw0 + 8 * i, sp = a.PR * pw + 8 * j;
+      int cost = 0;
+      for (int cls = 0; cls < (pair ? 2 : 1); ++cls)
+        for (int tx = 0; tx < KW; ++tx)
+          for (int h = 0; h < cols; h += 32) {            // one half wavefront's columns
+            int words[32], nw = 0, per_bank[32] = {0}, worst = 0;
+            for (int l = 0; l < 32; ++l) {
+              const int n = h + l, il = n >> a.lgP, y = (n & (P - 1)) >> a.lgWo, x = n & (Wo - 1);
+              const int word = (il * sp + y * S * pw + x * S + (pair ? cls - 1 : -1) + IG_MARGIN + tx) >> 1;
+              bool seen = false;
+              for (int q = 0; q < nw; ++q) seen = seen || words[q] == word;
+              if (!seen) { words[nw++] = word; worst = ++per_bank[word & 31] > worst ? per_bank[word & 31] : worst; }
+            }
+            cost += worst;
+          }
+      const int64_t key = (int64_t)cost * (1 << 20) + (int64_t)a.NI * sp;   // fewest conflicts first, then the smallest patch
+      if (best < 0 || key < best) { best = key; a.PW = pw; a.SP = sp; }
+    }
+  std::lock_guard<std::mutex> lock(ig_pitch_mutex);
+  if (ig_pitch_cache.size() < 256) ig_pitch_cache.push_back(IgPitchKey{KW, S, Ho, Wo, W, cols, (int)pair, a.PW, a.SP});
   return true;
 }
 
@@ -452,7 +497,7 @@ struct IgDwArgs {
   int64_t x_img, x_model, y_img, y_model;                // element strides: sample, model
   int64_t o_model, o_split;                              // output strides: model, k split
   int Nb, Ci, Co, H, W, Ho, Wo, lgWo, lgP;
-  int NI, PR, PW, nchunk;
+  int NI, PR, PW, SP, nchunk;                            // samples per k-tile, patch rows, row pitch, sample pitch (elements)
   int tiles_n, kt_total, kt_per_split;
   IgGrid grid;                                           // logical grid: x = tiles, y = k split, z = model
   uint32_t x_bytes, y_bytes;                             // extents of one model's slices of X and dY
@@ -464,7 +509,7 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
   auto As = [&](int buf) { return smem + buf * GEMM_TILE_BYTES; };
   auto Cb = [&](int buf) { return smem + 2 * GEMM_TILE_BYTES + buf * GEMM_TILE_BYTES; };
   bf16_raw* const Pt = reinterpret_cast<bf16_raw*>(smem + 4 * GEMM_TILE_BYTES);
-  const int chan_el = p.NI * p.PR * p.PW, patch_el = 8 * chan_el;
+  const int chan_el = p.NI * p.SP, patch_el = 8 * chan_el;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int bx, by, b;
@@ -490,7 +535,7 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
     p_row = r % p.PR; r /= p.PR;
     p_il = r % p.NI;
     const int c_l = r / p.NI;
-    p_lds = ((c_l * p.NI + p_il) * p.PR + p_row) * p.PW + IG_MARGIN + xc * 8;
+    p_lds = (c_l * p.NI + p_il) * p.SP + p_row * p.PW + IG_MARGIN + xc * 8;
     if (c0 + c_l < p.Ci) p_off = (uint32_t)(((int64_t)(c0 + c_l) * HW + xc * 8) * 2);
   }
   // this thread's part of the column tile: row j = t % 128, 16 consecutive k (pixels) as four groups of 4 in a row
@@ -502,7 +547,7 @@ __global__ __launch_bounds__(256) void conv_ig_dw_kernel(IgDwArgs p) {
     for (int g = 0; g < 4; ++g) {
       const int kl = bhalf * 16 + 4 * g;
       const int il = kl >> p.lgP, y_l = (kl & (P - 1)) >> p.lgWo, x = kl & (p.Wo - 1);
-      boff[g] = ((c_l * p.NI + il) * p.PR + 2 * y_l + ky) * p.PW + 2 * x + kx - 1 + IG_MARGIN;
+      boff[g] = (c_l * p.NI + il) * p.SP + (2 * y_l + ky) * p.PW + 2 * x + kx - 1 + IG_MARGIN;
     }
   }
   const int ga = t & 3, ra = t >> 2;
@@ -657,7 +702,7 @@ int conv_ig_forward(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
   a.M = Co; a.K = Ci * 16; a.N = Nb * Ho * Wo;
   if (!ig_extents(a)) return HFTA_EUNSUPPORTED;
   a.OW = Wo; a.oys = 1; a.oxs = 1; a.tap_step = 1;
-  ig_geometry(a, 4, 2, Ho, Wo, W, 128);
+  ig_geometry(a, 4, 4, 2, Ho, Wo, W, 128, false);
   const int tm = Co <= 64 ? 64 : 128;
   a.nchunk = 2 * a.NI * a.PR * (W / a.chunk_el);
   if (a.nchunk > 512) return HFTA_EUNSUPPORTED;
@@ -732,7 +777,7 @@ int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   a.M = Ci; a.K = Co * 4; a.N = Nb * Hq * Wq;
   if (!ig_extents(a)) return HFTA_EUNSUPPORTED;
   a.OW = W; a.oys = 2; a.oxs = 2; a.tap_step = 1;
-  ig_geometry(a, 2, 1, Hq, Wq, Wq, 64);
+  ig_geometry(a, 2, 2, 1, Hq, Wq, Wq, 64, true);
   const int tm = Ci <= 64 ? 64 : 128;
   a.nchunk = 8 * a.NI * a.PR * (Wq / a.chunk_el);
   if (a.nchunk > 512) return HFTA_EUNSUPPORTED;
@@ -814,7 +859,29 @@ int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   a.NI = P >= 32 ? 1 : 2;
   const int TR = P >= 32 ? 32 / Wo : Ho;
   a.PR = (TR - 1) * 2 + 4;
-  a.PW = W + 16;
+  {
+    // Row and sample pitch of the patch with the fewest LDS bank conflicts in the gather (32 banks of
+    // 4 bytes, 32 lanes per clock): the lanes of a half wavefront read the 16 taps of two channels.
+    int64_t best = -1;
+    for (int i = 0; i < 6; ++i)
+      for (int j = 0; j < 8; ++j) {
+        const int pw = W + 16 + 8 * i, sp = a.PR * pw + 8 * j;
+        int cost = 0;
+        for (int h = 0; h < 2; ++h) {
+          int words[32], nw = 0, per_bank[32] = {0}, worst = 0;
+          for (int l = 0; l < 32; ++l) {
+            const int bj = h * 32 + l, c_l = bj >> 4, ky = (bj >> 2) & 3, kx = bj & 3;
+            const int word = (c_l * a.NI * sp + ky * pw + kx + IG_MARGIN - 1) >> 1;
+            bool seen = false;
+            for (int q = 0; q < nw; ++q) seen = seen || words[q] == word;
+            if (!seen) { words[nw++] = word; worst = ++per_bank[word & 31] > worst ? per_bank[word & 31] : worst; }
+          }
+          cost += worst;
+        }
+        const int64_t key = (int64_t)cost * (1 << 20) + (int64_t)a.NI * sp;
+        if (best < 0 || key < best) { best = key; a.PW = pw; a.SP = sp; }
+      }
+  }
   a.nchunk = 8 * a.NI * a.PR * (W / 8);
   if (a.nchunk > 256 || W % 8 != 0) return HFTA_EUNSUPPORTED;
   const int64_t xb = ((int64_t)(Nb - 1) * a.x_img + (int64_t)Ci * H * W) * 2, yb = ((int64_t)(Nb - 1) * a.y_img + (int64_t)Co * P) * 2;
@@ -827,7 +894,7 @@ int conv_ig_dw(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   a.kt_per_split = (a.kt_total + splits - 1) / splits;
   a.o_split = (int64_t)B * a.o_model;
   a.Out = splits > 1 ? partial : dW;
-  const size_t k_loop = 4 * (size_t)GEMM_TILE_BYTES + (size_t)8 * a.NI * a.PR * a.PW * 2;
+  const size_t k_loop = 4 * (size_t)GEMM_TILE_BYTES + (size_t)8 * a.NI * a.SP * 2;
   const size_t staging = 64 * (size_t)EPI_PITCH4;
   const size_t lds = k_loop > staging ? k_loop : staging;
   if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
