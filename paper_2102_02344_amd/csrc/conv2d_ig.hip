@@ -469,20 +469,31 @@ size_t ig_lds_bytes(const IgArgs& a, int cpt, int a_rows) {
 // convolution: Wp[b][class = 2 py + px][c][k = (o, jy, jx)] = W[b][o][c][ry + 2 (1 - jy)][rx + 2 (1 - jx)]
 // with ry = (py + 1) % 2: the two taps per axis that reach pixels of that parity, in the order in
 // which the gradient rows / columns qy + py - 1 + jy they multiply ascend.
+// One thread per (model, input channel, output channel), output channels fastest: it reads its 4x4
+// window (32 contiguous bytes) and writes the four classes' 2x2 sub-windows as 8-byte pieces that
+// are contiguous across the threads of a wavefront.
 __global__ __launch_bounds__(256) void ig_pack_class_w_kernel(const bf16_raw* __restrict__ Wt, bf16_raw* __restrict__ Wp, int Ci,
                                                               int Co, int64_t count) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;   // (b, c, o)
   if (i >= count) return;
+  const int o = (int)(i % Co);
+  const int64_t r = i / Co;
+  const int c = (int)(r % Ci);
+  const int64_t b = r / Ci;
+  const uint4* src = reinterpret_cast<const uint4*>(Wt + ((b * Co + o) * Ci + c) * 16);
+  const uint4 lo = src[0], hi = src[1];                  // rows ky = 0, 1 | 2, 3; two taps per 32-bit word
+  const uint32_t w[4][2] = {{lo.x, lo.y}, {lo.z, lo.w}, {hi.x, hi.y}, {hi.z, hi.w}};
+  auto tap = [&](int ky, int kx) { return (w[ky][kx >> 1] >> (16 * (kx & 1))) & 0xffffu; };
   const int K = Co * 4;
-  const int kk = (int)(i % K);
-  int64_t r = i / K;
-  const int c = (int)(r % Ci); r /= Ci;
-  const int cls = (int)(r & 3);
-  const int64_t b = r >> 2;
-  const int py = cls >> 1, px = cls & 1;
-  const int ry = (py + 1) & 1, rx = (px + 1) & 1;
-  const int o = kk >> 2, jy = (kk >> 1) & 1, jx = kk & 1;
-  Wp[i] = Wt[((b * Co + o) * Ci + c) * 16 + (ry + 2 * (1 - jy)) * 4 + rx + 2 * (1 - jx)];
+#pragma unroll
+  for (int cls = 0; cls < 4; ++cls) {
+    const int py = cls >> 1, px = cls & 1;
+    const int ry = (py + 1) & 1, rx = (px + 1) & 1;
+    // k = (o, jy, jx) <- tap (ry + 2 (1 - jy), rx + 2 (1 - jx))
+    const uint32_t k01 = tap(ry + 2, rx + 2) | (tap(ry + 2, rx) << 16);
+    const uint32_t k23 = tap(ry, rx + 2) | (tap(ry, rx) << 16);
+    *reinterpret_cast<uint2*>(Wp + ((b * 4 + cls) * Ci + c) * K + o * 4) = make_uint2(k01, k23);
+  }
 }
 
 
@@ -791,7 +802,7 @@ int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
   const int tiles_m = (Ci + tm - 1) / tm;
   if ((int64_t)tiles_m * a.tiles_n > 0x7fffffff) return HFTA_EUNSUPPORTED;
-  const int64_t count = (int64_t)B * 4 * Ci * Co * 4;
+  const int64_t count = (int64_t)B * Ci * Co;
   hipLaunchKernelGGL(ig_pack_class_w_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, (const bf16_raw*)Wt,
                      (bf16_raw*)pack, Ci, Co, count);
   const int ktiles = (a.K + 31) / 32;
