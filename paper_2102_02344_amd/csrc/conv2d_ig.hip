@@ -846,8 +846,9 @@ bool conv_ig_dw_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, 
 int conv_ig_dw_splits(int B, int Nb, int Ci, int Co, int H, int W) {
   const int64_t kt_total = ((int64_t)Nb * (H / 2) * (W / 2) + 31) / 32;
   const int64_t tiles = (int64_t)((Co + 127) / 128) * ((Ci + 7) / 8) * B;
-  if (tiles >= 768 || kt_total < 32) return 1;
-  int64_t want = (1536 + tiles - 1) / tiles, cap = kt_total / 16;
+  if (tiles >= 512 || kt_total < 32) return 1;
+  // two workgroups per compute unit: more splits only add partial-slice traffic (measured 512 .. 1536)
+  int64_t want = (512 + tiles - 1) / tiles, cap = kt_total / 16;
   if (want > cap) want = cap;
   if (want > 64) want = 64;
   return want < 1 ? 1 : (int)want;
