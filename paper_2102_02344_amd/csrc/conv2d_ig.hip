@@ -119,9 +119,13 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
   static_assert(TM == 128 || TM == 64, "row tiles of 128 or 64");
   constexpr int TK = KH * KW, CPT = 32 / TK;             // taps per channel, channels per k-tile
   constexpr int NT = 256;
-  constexpr int AROWS = PAIR ? 2 * TM : TM;              // rows of the weight tile
+  constexpr int AROWS = TM;                              // rows of the weight tile (PAIR: none, see below)
   constexpr int NA = AROWS * 4 / NT;                     // 16-byte weight pieces per thread
-  constexpr int A_BYTES = AROWS * GEMM_PITCH;
+  // Weights as matrix-instruction fragments straight from memory: only where they are stored in
+  // fragment order (PAIR).  From the forward's row-major weights a wavefront's fragment load touches
+  // 32 rows of 64 bytes, and the kernel measured 1.3-1.5x slower than with the LDS tile.
+  constexpr bool AFRAG = PAIR;
+  constexpr int A_BYTES = AFRAG ? 0 : AROWS * GEMM_PITCH;
   constexpr int KPT = 16;                                // k per thread of the column tile
   constexpr int COLS = PAIR ? 64 : 128;                  // pixel columns per tile
   constexpr int FN = TM == 128 ? 2 : 1;                  // 32-column blocks per wavefront
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
   // position of the wavefront's block of the tile
   const int wm = TM == 128 ? wave >> 1 : 0;
   const int col0 = TM == 128 ? (wave & 1) * 64 : wave * 32;
-  const int a_row0 = (PAIR ? (col0 >> 6) * TM : 0) + wm * 64;
+  const int a_row0 = wm * 64;
 
   const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + (int64_t)b * p.x_model, p.x_bytes);
   const __amdgpu_buffer_rsrc_t rw = pf_rsrc(p.A + (int64_t)b * p.a_model, p.a_bytes);
@@ -190,22 +194,43 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
     boff = il * p.SP + ((y - y0) * S + (cl.oy - rmin)) * p.PW + x * S + cl.ox + IG_MARGIN;
     boff += ((bhalf * KPT) / TK) * chan_el;
   }
-  // ---- weight pieces: rows ra + 64 h of the weight tile, 8 k at ga
+  // ---- weights.  Forward: rows ra + 64 h of the weight tile, 8 k at ga, through LDS.
+  // PAIR: the regrouped weights are stored in the order the matrix instructions consume them
+  // ([class][row tile][k-tile][32-row block][k-step][lane][8 k], ig_pack_class_w_kernel), so a
+  // wavefront loads its own fragments -- 64 rows of its class, four 16-byte loads per lane, each a
+  // contiguous 1 KB per wavefront -- straight into registers: no LDS write, no LDS fragment read.
   const int ga = t & 3, ra = t >> 2;
   uint32_t wo[NA];
+  uint32_t fo = 0;                                        // PAIR: byte offset of this lane's first fragment of k-tile 0
+  if constexpr (PAIR) {
+    const int64_t tile_el = (int64_t)ktiles * TM * 32;    // one (class, row tile): every k-tile's TM x 32 block
+    fo = (uint32_t)((p.cls[py2 + (col0 >> 6)].a_off + (int64_t)tile_m * tile_el) * 2) + (uint32_t)((wm * 4 * 64 + lane) * 16);
 #pragma unroll
-  for (int h = 0; h < NA; ++h) {
-    const int r = ra + (NT / 4) * h;                      // PAIR: first TM rows class px = 0, then class px = 1
-    const int m = m0 + r % TM;
-    const int64_t a_off = PAIR ? p.cls[py2 + r / TM].a_off : cl0.a_off;
-    wo[h] = m < p.M ? (uint32_t)((a_off + (int64_t)m * p.K + ga * 8) * 2) : PF_OOB;
+    for (int h = 0; h < NA; ++h) wo[h] = PF_OOB;
+  } else {
+#pragma unroll
+    for (int h = 0; h < NA; ++h) {
+      const int r = ra + (NT / 4) * h;
+      const int m = m0 + r;
+      wo[h] = m < p.M ? (uint32_t)((cl0.a_off + (int64_t)m * p.K + ga * 8) * 2) : PF_OOB;
+    }
   }
   pf_u32x4 qa[NA], qp[2];
+  pf_u32x4 fa_cur[2][2], fa_nxt[2][2];                    // PAIR: fragments [32-row block][k-step] of this and the next k-tile
   auto issue_a = [&](int kt) {
-    const bool in_k = kt * 32 + ga * 8 + 8 <= p.K;
+    if constexpr (PAIR) {
 #pragma unroll
-    for (int h = 0; h < NA; ++h)
-      qa[h] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)((in_k && wo[h] != PF_OOB) ? wo[h] + (uint32_t)kt * 64u : PF_OOB), 0, 0);
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+          fa_nxt[i][s2] = __builtin_amdgcn_raw_buffer_load_b128(
+              rw, (int)(kt < ktiles ? fo + (uint32_t)kt * (uint32_t)(TM * 64) + (uint32_t)((i * 2 + s2) * 1024) : PF_OOB), 0, 0);
+    } else {
+      const bool in_k = kt * 32 + ga * 8 + 8 <= p.K;
+#pragma unroll
+      for (int h = 0; h < NA; ++h)
+        qa[h] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)((in_k && wo[h] != PF_OOB) ? wo[h] + (uint32_t)kt * 64u : PF_OOB), 0, 0);
+    }
   };
   auto issue_p = [&](int kt) {
     const int c0 = kt * CPT;
@@ -221,8 +246,15 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
     }
   };
   auto park_a = [&](int buf) {
+    if constexpr (AFRAG) {
 #pragma unroll
-    for (int h = 0; h < NA; ++h) *reinterpret_cast<pf_u32x4*>(As(buf) + (ra + (NT / 4) * h) * GEMM_PITCH + ga * 16) = qa[h];
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) fa_cur[i][s2] = fa_nxt[i][s2];
+    } else {
+#pragma unroll
+      for (int h = 0; h < NA; ++h) *reinterpret_cast<pf_u32x4*>(As(buf) + (ra + (NT / 4) * h) * GEMM_PITCH + ga * 16) = qa[h];
+    }
   };
   auto park_p = [&](int buf) {
 #pragma unroll
@@ -269,7 +301,10 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
     for (int s = 0; s < 2; ++s) {
       bf16x8_t a[2], bq[FN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(Ab + i * 32 * GEMM_PITCH + s * 32);
+      for (int i = 0; i < 2; ++i) {
+        if constexpr (AFRAG) a[i] = __builtin_bit_cast(bf16x8_t, fa_cur[i][s]);
+        else a[i] = *reinterpret_cast<const bf16x8_t*>(Ab + i * 32 * GEMM_PITCH + s * 32);
+      }
 #pragma unroll
       for (int j = 0; j < FN; ++j) bq[j] = *reinterpret_cast<const bf16x8_t*>(Bb + j * 32 * GEMM_PITCH + s * 32);
 #pragma unroll
@@ -297,11 +332,11 @@ __global__ __launch_bounds__(256) void conv_ig_fwd_kernel(IgArgs p) {
   for (int kt = kt0; kt < kt1; ++kt) {
     const int buf = (kt - kt0) & 1;
     build_read(buf ^ 1);                                  // gather of column tile kt + 1 (patch kt + 1 was parked an iteration ago)
-    park_a(buf ^ 1);                                      // weights kt + 1
+    if constexpr (!AFRAG) { park_a(buf ^ 1); issue_a(kt + 2); }  // weights kt + 1 -> LDS, kt + 2 requested
     park_p(buf);                                          // patch kt + 2
-    issue_a(kt + 2);
     issue_p(kt + 3);
     mma(buf);
+    if constexpr (AFRAG) { park_a(0); issue_a(kt + 2); }  // fragments kt + 1 become current, kt + 2 requested
     build_write(buf ^ 1);
     __syncthreads();
   }
@@ -466,34 +501,46 @@ size_t ig_lds_bytes(const IgArgs& a, int cpt, int a_rows) {
 }
 
 // Weights regrouped per output-parity class for the data gradient of a 4x4 / stride 2 / pad 1
-// convolution: Wp[b][class = 2 py + px][c][k = (o, jy, jx)] = W[b][o][c][ry + 2 (1 - jy)][rx + 2 (1 - jx)]
-// with ry = (py + 1) % 2: the two taps per axis that reach pixels of that parity, in the order in
-// which the gradient rows / columns qy + py - 1 + jy they multiply ascend.
-// One thread per (model, input channel, output channel), output channels fastest: it reads its 4x4
-// window (32 contiguous bytes) and writes the four classes' 2x2 sub-windows as 8-byte pieces that
-// are contiguous across the threads of a wavefront.
+// convolution, Wc[class = 2 py + px][c][k = (o, jy, jx)] = W[o][c][ry + 2 (1 - jy)][rx + 2 (1 - jx)] with
+// ry = (py + 1) % 2 (the two taps per axis that reach pixels of that parity, in the order in which
+// the gradient rows / columns qy + py - 1 + jy they multiply ascend), and stored in the order the
+// matrix instructions consume them:
+//   Wp[b][class][row tile][k-tile][32-row block][k-step (16 k)][lane][8 k],
+//   lane = 32 (k half) + row inside the block; rows past Ci and k past 4 Co are zeros.
+// One thread per 16-byte fragment piece: 8 k = the class's 2x2 taps of two output channels of one
+// input channel, read as two 32-byte windows; consecutive lanes read consecutive channels and
+// write consecutive pieces.
 __global__ __launch_bounds__(256) void ig_pack_class_w_kernel(const bf16_raw* __restrict__ Wt, bf16_raw* __restrict__ Wp, int Ci,
-                                                              int Co, int64_t count) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;   // (b, c, o)
+                                                              int Co, int tm, int tiles_m, int ktiles, int64_t count) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= count) return;
-  const int o = (int)(i % Co);
-  const int64_t r = i / Co;
-  const int c = (int)(r % Ci);
-  const int64_t b = r / Ci;
-  const uint4* src = reinterpret_cast<const uint4*>(Wt + ((b * Co + o) * Ci + c) * 16);
-  const uint4 lo = src[0], hi = src[1];                  // rows ky = 0, 1 | 2, 3; two taps per 32-bit word
-  const uint32_t w[4][2] = {{lo.x, lo.y}, {lo.z, lo.w}, {hi.x, hi.y}, {hi.z, hi.w}};
-  auto tap = [&](int ky, int kx) { return (w[ky][kx >> 1] >> (16 * (kx & 1))) & 0xffffu; };
-  const int K = Co * 4;
+  const int lane = (int)(i & 63), s2 = (int)((i >> 6) & 1);
+  int64_t r = i >> 7;
+  const int rbs = tm / 32;
+  const int rb = (int)(r % rbs); r /= rbs;
+  const int kt = (int)(r % ktiles); r /= ktiles;
+  const int tile_m = (int)(r % tiles_m); r /= tiles_m;
+  const int cls = (int)(r & 3);
+  const int64_t b = r >> 2;
+  const int c = tile_m * tm + rb * 32 + (lane & 31);
+  const int o0 = (kt * 32 + s2 * 16 + (lane >> 5) * 8) >> 2;       // two output channels: o0, o0 + 1
+  const int py = cls >> 1, px = cls & 1;
+  const int ry = (py + 1) & 1, rx = (px + 1) & 1;
+  uint32_t out[4] = {0u, 0u, 0u, 0u};
+  if (c < Ci) {
 #pragma unroll
-  for (int cls = 0; cls < 4; ++cls) {
-    const int py = cls >> 1, px = cls & 1;
-    const int ry = (py + 1) & 1, rx = (px + 1) & 1;
-    // k = (o, jy, jx) <- tap (ry + 2 (1 - jy), rx + 2 (1 - jx))
-    const uint32_t k01 = tap(ry + 2, rx + 2) | (tap(ry + 2, rx) << 16);
-    const uint32_t k23 = tap(ry, rx + 2) | (tap(ry, rx) << 16);
-    *reinterpret_cast<uint2*>(Wp + ((b * 4 + cls) * Ci + c) * K + o * 4) = make_uint2(k01, k23);
+    for (int q = 0; q < 2; ++q) {
+      if (o0 + q < Co) {
+        const uint4* src = reinterpret_cast<const uint4*>(Wt + ((b * Co + o0 + q) * Ci + c) * 16);
+        const uint4 lo = src[0], hi = src[1];              // rows ky = 0, 1 | 2, 3; two taps per 32-bit word
+        const uint32_t w[4][2] = {{lo.x, lo.y}, {lo.z, lo.w}, {hi.x, hi.y}, {hi.z, hi.w}};
+        auto tap = [&](int ky, int kx) { return (w[ky][kx >> 1] >> (16 * (kx & 1))) & 0xffffu; };
+        out[2 * q] = tap(ry + 2, rx + 2) | (tap(ry + 2, rx) << 16);      // (jy, jx) = (0, 0), (0, 1)
+        out[2 * q + 1] = tap(ry, rx + 2) | (tap(ry, rx) << 16);          // (1, 0), (1, 1)
+      }
+    }
   }
+  *reinterpret_cast<uint4*>(Wp + i * 8) = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
 
@@ -751,8 +798,9 @@ namespace hfta {
 // four parity classes (grid.y = py, the two px of a tile side by side), each a stride-1 2x2 correlation
 // over dY with its regrouped weights.
 // `pack` receives the regrouped weights: conv_ig_dx_pack_bytes(...) bytes, 16-byte aligned.
-size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co) {                  // rounded up to 256 bytes
-  return ((size_t)B * 4 * Ci * Co * 4 * sizeof(bf16_raw) + 255) & ~(size_t)255;
+size_t conv_ig_dx_pack_bytes(int B, int Ci, int Co) {                  // whole row tiles and k-tiles; a multiple of 256 bytes
+  const int tm = Ci <= 64 ? 64 : 128, tiles_m = (Ci + tm - 1) / tm, ktiles = (Co * 4 + 31) / 32;
+  return (size_t)B * 4 * tiles_m * tm * ktiles * 32 * sizeof(bf16_raw);
 }
 
 bool conv_ig_dx_supported(int Nb, int Ci, int Co, int H, int W, int kh, int kw, int stride, int pad) {
@@ -782,35 +830,34 @@ int conv_ig_dx(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw, int 
   IgArgs a{};
   a.X = (const bf16_raw*)dY; a.A = (const bf16_raw*)pack; a.Out = (bf16_raw*)dX; a.bias = nullptr;
   a.x_img = (int64_t)B * Co * Hq * Wq; a.x_model = (int64_t)Co * Hq * Wq;
-  a.a_model = (int64_t)4 * Ci * Co * 4;
+  const int tm = Ci <= 64 ? 64 : 128, tiles_m = (Ci + tm - 1) / tm, ktiles = (Co * 4 + 31) / 32;
+  const int64_t cls_el = (int64_t)tiles_m * tm * ktiles * 32;          // one class of one model, fragment order
+  a.a_model = 4 * cls_el;
   a.o_img = (int64_t)B * Ci * H * W; a.o_model = (int64_t)Ci * H * W; a.o_m = (int64_t)H * W;
   a.Nb = Nb; a.Cx = Co; a.H = Hq; a.W = Wq;
   a.M = Ci; a.K = Co * 4; a.N = Nb * Hq * Wq;
   if (!ig_extents(a)) return HFTA_EUNSUPPORTED;
   a.OW = W; a.oys = 2; a.oxs = 2; a.tap_step = 1;
   ig_geometry(a, 2, 2, 1, Hq, Wq, Wq, 64, true);
-  const int tm = Ci <= 64 ? 64 : 128;
   a.nchunk = 8 * a.NI * a.PR * (Wq / a.chunk_el);
   if (a.nchunk > 512) return HFTA_EUNSUPPORTED;
   a.tiles_n = (a.N + 63) / 64;
   a.act = HFTA_ACT_NONE; a.slope = 0.f;
   for (int cls = 0; cls < 4; ++cls) {
     const int py = cls >> 1, px = cls & 1;
-    a.cls[cls] = IgClass{py - 1, px - 1, py, px, (int64_t)cls * Ci * Co * 4};   // window rows qy + py - 1, qy + py
+    a.cls[cls] = IgClass{py - 1, px - 1, py, px, cls * cls_el};          // window rows qy + py - 1, qy + py
   }
-  const size_t lds = ig_lds_bytes(a, 8, 2 * tm);
+  const size_t lds = ig_lds_bytes(a, 8, 0);
   if (lds > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
-  const int tiles_m = (Ci + tm - 1) / tm;
   if ((int64_t)tiles_m * a.tiles_n > 0x7fffffff) return HFTA_EUNSUPPORTED;
-  const int64_t count = (int64_t)B * Ci * Co;
+  const int64_t count = (int64_t)B * 4 * cls_el / 8;                   // 16-byte fragment pieces
   hipLaunchKernelGGL(ig_pack_class_w_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, (const bf16_raw*)Wt,
-                     (bf16_raw*)pack, Ci, Co, count);
-  const int ktiles = (a.K + 31) / 32;
+                     (bf16_raw*)pack, Ci, Co, tm, tiles_m, ktiles, count);
   a.ksplit = (split_ws && reinterpret_cast<uintptr_t>(split_ws) % 16 == 0) ? ig_pick_ksplit((int64_t)tiles_m * a.tiles_n * 2 * B, ktiles, true) : 1;
   a.kt_per_split = (ktiles + a.ksplit - 1) / a.ksplit;
   a.part = reinterpret_cast<float*>(split_ws);
   a.part_split = (int64_t)Nb * a.o_img;
-  const size_t lds2 = ig_lds_bytes(a, 8, 2 * tm);
+  const size_t lds2 = ig_lds_bytes(a, 8, 0);
   if (lds2 > IG_MAX_LDS) return HFTA_EUNSUPPORTED;
   dim3 grid((unsigned)(tiles_m * a.tiles_n), (unsigned)(2 * a.ksplit), (unsigned)B);
   if (a.chunk_el == 8) {
