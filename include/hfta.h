@@ -175,9 +175,16 @@ int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
  *   ConvT bwd-data = hfta_conv2d_grouped_fwd; ConvT dW = hfta_conv2d_grouped_bwd's dW with the
  *              roles of X and dY exchanged the same way.
  * ---------------------------------------------------------------------- */
-/* workspace (optional, 256-byte aligned): with at least hfta_conv2d_grouped_fwd_workspace_bytes the
- * convolution is lowered through a column buffer onto the batched GEMM kernels (sample index folded
- * into the GEMM's columns); with NULL / less it runs as an implicit GEMM per (model, sample). */
+/* Which kernels run (results agree to the storage tolerance, up to fp32 summation order):
+ *  - bf16, 4x4 kernel, stride 2, pad 1, output sides powers of two (>= 4): an implicit GEMM with the
+ *    samples folded into the GEMM's columns; needs no workspace.  With a 16-byte aligned workspace of
+ *    hfta_conv2d_grouped_fwd_workspace_bytes, layers with few output tiles and a long reduction
+ *    split the reduction and keep fp32 partial slices there.
+ *  - kernel = image and pad 0 (one output pixel): the fused Linear over the flattened window.
+ *  - everything else (other kernels / strides, odd grids, fp32): with a 256-byte aligned workspace of
+ *    hfta_conv2d_grouped_fwd_workspace_bytes the convolution is lowered through a column buffer onto
+ *    the batched GEMM kernels; with NULL / less it runs as an implicit GEMM per (model, sample).
+ * The workspace is scratch: nothing in it is read from an earlier call or kept for a later one. */
 size_t hfta_conv2d_grouped_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W,
                                                int kh, int kw, int stride, int pad, int dtype);
 int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh, int kw,
@@ -186,9 +193,15 @@ int hfta_conv2d_grouped_fwd(int B, int Nb, int Ci, int Co, int H, int W, int kh,
                             int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
 
 /* dX:[Nb][B*Ci][H][W] storage dtype (NULL = skip); dW: fp32 [B*Co][Ci][kh][kw] (NULL = skip);
- * dbias: fp32 [B*Co] (NULL = skip).  hfta_conv2d_grouped_bwd_workspace_bytes is the size that
- * enables the column-buffer path; a smaller workspace (down to the implicit path's split-K
- * partials, possibly none) selects the implicit GEMM kernels. */
+ * dbias: fp32 [B*Co] (NULL = skip).
+ * Workspace (256-byte aligned): hfta_conv2d_grouped_bwd_min_workspace_bytes is what the implicit-GEMM
+ * kernels need -- the weight gradient's split partials and, for the bf16 4x4 / stride 2 / pad 1
+ * shapes, the data gradient's weights regrouped per output-parity class (rewritten on every call) --
+ * and may be 0; with less, the data gradient falls back to a kernel that gathers single taps and a
+ * split weight gradient returns HFTA_EWORKSPACE.  hfta_conv2d_grouped_bwd_workspace_bytes (>= the
+ * minimum) additionally enables the column-buffer lowering for the shapes that have no
+ * sample-folded kernel.  At most 4 input channels (bf16, 4x4 / stride 2 / pad 1): the data gradient
+ * is computed by direct vector arithmetic and needs no workspace. */
 size_t hfta_conv2d_grouped_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W,
                                                int kh, int kw, int stride, int pad, int dtype);
 size_t hfta_conv2d_grouped_bwd_min_workspace_bytes(int B, int Nb, int Ci, int Co, int H, int W,
