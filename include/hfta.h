@@ -20,8 +20,10 @@
  *    owns all memory; the library allocates nothing, frees nothing and keeps
  *    no pointer after the call returns.  The only state it keeps between calls
  *    is read-only after its first use: the compute-unit count of the device
- *    (queried once, sizes the persistent GEMM launches) and, for
- *    hfta_linear_fwd_static, the address of its built-in scratch array.  Scratch memory is a caller-supplied
+ *    (queried once, sizes the persistent GEMM launches), for
+ *    hfta_linear_fwd_static the address of its built-in scratch array, and a
+ *    memo of LDS pitches per convolution geometry (a pure function of the
+ *    shape, computed on the host the first time a shape is seen).  Scratch memory is a caller-supplied
  *    `workspace` whose required size the matching *_workspace_bytes function
  *    returns (0 = none needed; then NULL is accepted).
  *  - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =
