@@ -40,7 +40,7 @@ class Tracer:
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
                      "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
                      "point_transform_fwd", "point_transform_bwd",
-                     "conv1x1_bn_maxpool_bwd")
+                     "conv1x1_bn_maxpool_bwd", "conv1x1_bn_fwd")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -88,6 +88,11 @@ def kernel_label(name, a):
     if name in ("bn_fwd", "bn_bwd"):
         lay = "linear" if a[3] == 1 else "conv"
         return f"{name}_{lay}_kernel"
+    if name == "conv1x1_bn_fwd":
+        B, Nb, Ci, Co, L, dt = a[:6]
+        if dt == 1 and Ci % 8 == 0 and L % 4 == 0 and ((Ci <= 128 and Co >= 64) or (Ci <= 256 and Co >= 512)):
+            return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_fwd_conv_part_kernel"
+        return "conv1x1_bn_fwd: conv1x1 kernel + bn_fwd_conv_kernel"
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci <= 4 and L % 4 == 0:
@@ -215,7 +220,7 @@ def algorithmic_flops(name, a):
             return 0.0
         both = name == "linear_bwd" and a[8] is not None and a[9] is not None
         return (4.0 if both else 2.0) * B * M * Fx * Fy
-    if name in ("conv1x1_fwd", "conv1x1_bwd"):
+    if name in ("conv1x1_fwd", "conv1x1_bwd", "conv1x1_bn_fwd"):
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * Co * L
     if name in ("attention_fwd", "attention_bwd"):      # 2 (forward) / 4 (backward) products of S x S x d per head
@@ -251,6 +256,9 @@ def algorithmic_bytes(name, a):
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         return (B * Nb * (Ci + Co) * L + B * Co * (Ci + 1)) * _es(dt)
+    if name == "conv1x1_bn_fwd":       # x and W in, z out; z in, y out
+        B, Nb, Ci, Co, L, dt = a[:6]
+        return (B * Nb * (Ci + 3 * Co) * L + B * Co * (Ci + 1)) * _es(dt)
     if name in ("linear_fwd", "linear_fwd_ws"):
         B, M, Fx, Fy, dt = a[:5]
         return B * (M * Fx + Fx * Fy + Fy + M * Fy) * _es(dt)

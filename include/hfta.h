@@ -148,6 +148,24 @@ int hfta_conv1x1_fwd_sample_bias(int B, int Nb, int Ci, int Co, int L, int dtype
                                  const void* S, const int64_t ss[3],
                                  void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
 
+/* Fused Conv1d k=1 followed by training-mode BatchNorm and an activation (the per-point layers of
+ * the point-cloud models; rows "Conv1d" and "BatchNorm1d" of the fusion rules table):
+ *   Z = W X + bias                        (stored with strides zs: the BatchNorm backward reads it)
+ *   Y = act(gamma (Z - mean) invstd + beta), statistics over (n, l) per (b, c) of the STORED Z.
+ * Arguments as in hfta_conv1x1_fwd and hfta_bn_fwd; act in {NONE, RELU, LEAKY} applies to Y.
+ * Results equal hfta_conv1x1_fwd followed by hfta_bn_fwd up to the fp32 summation order of the
+ * statistics.  With a workspace of hfta_conv1x1_bn_fwd_workspace_bytes (8-byte aligned) and a bf16
+ * layer that the streaming convolution kernel takes, the convolution's epilogue leaves per-slice
+ * sums there and Z is read once (for the normalisation) instead of twice; otherwise the two
+ * operators run one after the other (no workspace needed). */
+size_t hfta_conv1x1_bn_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
+int hfta_conv1x1_bn_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                        const void* X, const int64_t xs[4], const void* W, const void* bias,
+                        const float* gamma, const float* beta, float eps, float momentum,
+                        float* running_mean, float* running_var, float* save_mean, float* save_invstd,
+                        void* Z, const int64_t zs[4], void* Y, const int64_t ys[4],
+                        int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
+
 /* Backward: dX[b,n,c,l] = sum_o W[b,o,c] dY[b,n,o,l]   (storage dtype, strides dxs; NULL = skip)
  *           dW[b,o,c]   = sum_{n,l} dY[b,n,o,l] X[b,n,c,l]   (fp32; NULL = skip)
  *           dbias[b,o]  = sum_{n,l} dY[b,n,o,l]              (fp32; NULL = skip)

@@ -223,7 +223,8 @@ class FusedPointNetCls(ParamArena):
         self.loss = torch.empty(B, **f32)
         ws = 4
         for i in range(self.nconv):
-            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt),
+                     hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nfc):
             ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt),
                      hb.linear_fwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt))
@@ -268,6 +269,19 @@ class FusedPointNetCls(ParamArena):
                 self._layer_fwd_unfused(i, x, ci, co)
                 x, ci = self.a[i], co
                 continue
+            if i < self.nconv - 1:
+                # convolution + BatchNorm + ReLU in one call: the convolution's epilogue leaves the
+                # statistics' partial sums, so z is read once for the normalisation
+                hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
+                                  self.master(k + ".bn.g"), self.master(k + ".bn.b"), eps, mom,
+                                  self.running[k + ".bn.rm"], self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"],
+                                  self.saved[k + ".bn.invstd"], self.z[i], _cs(B, co, L), self.a[i], _cs(B, co, L),
+                                  hb.ACT_RELU, 0.0, self.ws)
+                P("conv1x1_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
+                P("bn_fwd", layer=k, layout="conv", x=self.z[i], g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"),
+                  y=self.a[i], mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"])
+                x, ci = self.a[i], co
+                continue
             hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
                            self.z[i], _cs(B, co, L))
             P("conv1x1_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
@@ -284,12 +298,6 @@ class FusedPointNetCls(ParamArena):
                   invstd=self.saved[k + ".bn.invstd"])
                 ci = co
                 break
-            hb.bn_fwd(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), self.master(k + ".bn.g"), self.master(k + ".bn.b"),
-                      eps, mom, self.running[k + ".bn.rm"], self.running[k + ".bn.rv"],
-                      self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"], self.a[i], _cs(B, co, L), hb.ACT_RELU)
-            P("bn_fwd", layer=k, layout="conv", x=self.z[i], g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"),
-              y=self.a[i], mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"])
-            x, ci = self.a[i], co
         Cp = ci
         # head
         h, fx = self.pooled, s.fc[0]
@@ -441,13 +449,13 @@ def _unfused_methods():
         B, Nb, L, dt, k = self.B, self.Nb, self.L, self.dt, f"conv{i}"
         xs, cs = _cs(B, ci, L), _cs(B, co, L)
         for b in range(B):
-            hb.conv1x1_fwd(1, Nb, ci, co, L, dt, _off(x, b * ci * L), xs, _off(self.w(k + ".w"), b * co * ci),
-                           _off(self.w(k + ".b"), b * co), _off(self.z[i], b * co * L), cs)
-            hb.bn_fwd(1, Nb, co, L, dt, _off(self.z[i], b * co * L), cs, _off(self.master(k + ".bn.g"), b * co),
-                      _off(self.master(k + ".bn.b"), b * co), self.BN_EPS, self.BN_MOMENTUM,
-                      _off(self.running[k + ".bn.rm"], b * co), _off(self.running[k + ".bn.rv"], b * co),
-                      _off(self.saved[k + ".bn.mean"], b * co), _off(self.saved[k + ".bn.invstd"], b * co),
-                      _off(self.a[i], b * co * L), cs, hb.ACT_RELU)
+            # the same operator as the fused array's (convolution + BatchNorm + ReLU), one model at a time
+            hb.conv1x1_bn_fwd(1, Nb, ci, co, L, dt, _off(x, b * ci * L), xs, _off(self.w(k + ".w"), b * co * ci),
+                              _off(self.w(k + ".b"), b * co), _off(self.master(k + ".bn.g"), b * co),
+                              _off(self.master(k + ".bn.b"), b * co), self.BN_EPS, self.BN_MOMENTUM,
+                              _off(self.running[k + ".bn.rm"], b * co), _off(self.running[k + ".bn.rv"], b * co),
+                              _off(self.saved[k + ".bn.mean"], b * co), _off(self.saved[k + ".bn.invstd"], b * co),
+                              _off(self.z[i], b * co * L), cs, _off(self.a[i], b * co * L), cs, hb.ACT_RELU, 0.0, self.ws)
 
     def _layer_bwd_unfused(self, i, xin, ci, co, da, dz, dxin):
         B, Nb, L, dt, k = self.B, self.Nb, self.L, self.dt, f"conv{i}"
@@ -907,9 +915,11 @@ class FusedPointNetSeg(ParamArena):
         ws = max(4, hb.softmax_xent_points_workspace_bytes(B, Nb, L), hb.linear_bwd_workspace_bytes(B, Nb, Cg, H[1], self.dt),
                  hb.linear_fwd_workspace_bytes(B, Nb, Cg, H[1], self.dt))
         for i in range(self.nconv):
-            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt),
+                     hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nh):
-            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, Cp if i == 0 else H[i], H[i + 1], L, self.dt))
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, Cp if i == 0 else H[i], H[i + 1], L, self.dt),
+                     hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, Cp if i == 0 else H[i], H[i + 1], L, self.dt))
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         self.points = torch.from_numpy(inp["points"]).to(self.tdt).to(self.dev)
         self.labels = torch.from_numpy(inp["labels"]).to(self.dev)
@@ -948,11 +958,12 @@ class FusedPointNetSeg(ParamArena):
         x, xs, xv, ci = self.points, _cs(B, 3, L), self.points, 3
         for i in range(self.nconv):
             co, k = s.conv[i + 1], f"conv{i}"
-            hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, xs, self.w(k + ".w"), self.w(k + ".b"), self.z[i], _cs(B, co, L))
-            P("conv1x1_fwd", layer=k, x=xv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
             a, av = self._slice(self.cat, i)
-            hb.bn_fwd(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *bn(k), eps, mom, self.running[k + ".bn.rm"],
-                      self.running[k + ".bn.rv"], *st(k), a, cst, hb.ACT_RELU)
+            # convolution + BatchNorm + ReLU in one call (z is read once, for the normalisation)
+            hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, x, xs, self.w(k + ".w"), self.w(k + ".b"), *bn(k), eps, mom,
+                              self.running[k + ".bn.rm"], self.running[k + ".bn.rv"], *st(k), self.z[i], _cs(B, co, L),
+                              a, cst, hb.ACT_RELU, 0.0, self.ws)
+            P("conv1x1_fwd", layer=k, x=xv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
             P("bn_fwd", layer=k, x=self.z[i], g=bn(k)[0], b=bn(k)[1], y=av, mean=st(k)[0], invstd=st(k)[1])
             x, xs, xv, ci = a, cst, av, co
         hb.maxpool_points(B, Nb, C4, L, dt, x, cst, self.gfeat, self.pool_idx, self.gvs)
@@ -969,13 +980,19 @@ class FusedPointNetSeg(ParamArena):
                 hb.conv1x1_fwd_sample_bias(B, Nb, ci, co, L, dt, h, hs, self.w(k + ".w"), self.hg, (Nb * co, co, 1),
                                            self.zh[i], cs)
                 P("conv1x1_fwd_sample_bias", layer=k, x=hv, w=self.w(k + ".w"), s=self.hg, y=self.zh[i])
+            elif i < self.nh - 1:
+                hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, h, hs, self.w(k + ".w"), self.w(k + ".b"), *bn(k), eps, mom,
+                                  self.running[k + ".bn.rm"], self.running[k + ".bn.rv"], *st(k), self.zh[i], cs,
+                                  self.ah[i], cs, hb.ACT_RELU, 0.0, self.ws)
+                P("conv1x1_fwd", layer=k, x=hv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.zh[i])
             else:
                 hb.conv1x1_fwd(B, Nb, ci, co, L, dt, h, hs, self.w(k + ".w"), self.w(k + ".b"), self.zh[i], cs)
                 P("conv1x1_fwd", layer=k, x=hv, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.zh[i])
             if i == self.nh - 1:
                 break
-            hb.bn_fwd(B, Nb, co, L, dt, self.zh[i], cs, *bn(k), eps, mom, self.running[k + ".bn.rm"],
-                      self.running[k + ".bn.rv"], *st(k), self.ah[i], cs, hb.ACT_RELU)
+            if i == 0:
+                hb.bn_fwd(B, Nb, co, L, dt, self.zh[i], cs, *bn(k), eps, mom, self.running[k + ".bn.rm"],
+                          self.running[k + ".bn.rv"], *st(k), self.ah[i], cs, hb.ACT_RELU)
             P("bn_fwd", layer=k, x=self.zh[i], g=bn(k)[0], b=bn(k)[1], y=self.ah[i], mean=st(k)[0], invstd=st(k)[1])
             h, hs, hv, ci = self.ah[i], cs, self.ah[i], co
         K = H[-1]
@@ -1201,7 +1218,8 @@ class _PointChain:
         cmax = max(self.conv)
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
         for i in range(self.nconv):
-            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt))
+            ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt),
+                     hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt))
         if self.head:
             Cp = self.conv[-1]
             self.pooled = torch.empty(B, Nb, Cp, **act)
@@ -1237,13 +1255,15 @@ class _PointChain:
                                           self.pooled, self.pool_idx, (Nb * co, co, 1), self.zhit, self.moments,
                                           hb.ACT_RELU, 0.0, ws)
                 break
+            if not tail:
+                hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), A.w(k + ".w"), A.w(k + ".b"), *self._bn(k),
+                                  self.z[i], _cs(B, co, L), self.a[i], _cs(B, co, L), hb.ACT_RELU, 0.0, ws)
+                x, ci = self.a[i], co
+                continue
             hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), A.w(k + ".w"), A.w(k + ".b"), self.z[i], _cs(B, co, L))
-            if tail:
-                hb.bn_fwd_maxpool(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *self._bn(k), self.pooled, self.pool_idx,
-                                  (Nb * co, co, 1), hb.ACT_RELU)
-                break
-            hb.bn_fwd(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *self._bn(k), self.a[i], _cs(B, co, L), hb.ACT_RELU)
-            x, ci = self.a[i], co
+            hb.bn_fwd_maxpool(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *self._bn(k), self.pooled, self.pool_idx,
+                              (Nb * co, co, 1), hb.ACT_RELU)
+            break
         if not self.head:
             return x
         h = self.pooled

@@ -31,6 +31,10 @@ struct StreamArgs {
   int act, c_vec;
   float slope;
   uint32_t w_extent, x_extent;
+  // BatchNorm statistics of the output, taken from the values as they are stored (nullptr: off):
+  // per (model, sample, 128-point slice) and channel the sums of (y - bias) and (y - bias)^2 over the
+  // slice's points, [b * Nb + n][slice][Co][2]; the activation must be none.
+  float* stat_part;
 };
 
 // ONE: the layer has a single 128-row W tile (Co <= 128), so the X tile is dead once the matrix
@@ -149,17 +153,43 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
     }
     __syncthreads();                     // every wavefront is done with the W tile
     store_tile<bf16_raw, bf16_raw, false>(acc, Ws, Yb, p.y_ld, p.Co, p.L, ct * 128, l0, bias, 1, p.act, p.slope, p.c_vec, t);
+    if (p.stat_part) {
+      // the staged tile [128 channels][128 points] is still in LDS: two threads per channel add their
+      // 64 points (rounded values, shifted by the channel's bias so that fp32 keeps its accuracy)
+      const int row = t >> 1, half = t & 1;
+      const int m = ct * 128 + row;
+      const float shift = (bias && m < p.Co) ? bf16_to_f32(bias[m]) : 0.f;
+      const unsigned char* src = Ws + row * EPI_PITCH2 + half * 128;
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const uint2 v = *reinterpret_cast<const uint2*>(src + q * 8);
+        const float z[4] = {__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                            __uint_as_float(v.y & 0xffff0000u)};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float d = (l0 + half * 64 + q * 4 + e < p.L) ? z[e] - shift : 0.f;
+          s1 += d;
+          s2 = fmaf(d, d, s2);
+        }
+      }
+      s1 += __shfl_xor(s1, 1, 64);
+      s2 += __shfl_xor(s2, 1, 64);
+      if (half == 0 && m < p.Co)
+        *reinterpret_cast<float2*>(p.stat_part + (((int64_t)bz * gridDim.x + bx) * p.Co + m) * 2) = make_float2(s1, s2);
+    }
     __syncthreads();                     // staging tile read out before the next W tile lands
   }
 }
 
 // Returns HFTA_OK when launched, HFTA_EUNSUPPORTED when the problem is not this kernel's.
 int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
-                       const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st) {
+                       const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st,
+                       float* stat_part) {
   auto al = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; };
   if (Ci > 256 || Ci % 8 != 0 || Co < 64 || L % 4 != 0) return HFTA_EUNSUPPORTED;
   if (Ci > 128 && Co < STREAM_WIDE_MIN_CO) return HFTA_EUNSUPPORTED;
-  if (act == HFTA_ACT_TANH || act == HFTA_ACT_GELU) return HFTA_EUNSUPPORTED;
+  if (act == HFTA_ACT_TANH || act == HFTA_ACT_GELU || (stat_part && act != HFTA_ACT_NONE)) return HFTA_EUNSUPPORTED;
   if (!al(W, 16) || !al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0) return HFTA_EUNSUPPORTED;
   const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2, w_ext = (int64_t)Co * Ci * 2;
   if (x_ext >= (int64_t)1 << 31 || w_ext >= (int64_t)1 << 31) return HFTA_EUNSUPPORTED;
@@ -176,6 +206,7 @@ int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, cons
     if (al(Y, w) && ys[0] % q == 0 && ys[1] % q == 0 && ys[2] % q == 0) { a.c_vec = w; break; }
   }
   a.w_extent = (uint32_t)w_ext; a.x_extent = (uint32_t)x_ext;
+  a.stat_part = stat_part;
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
   if (Ci <= 64 && Co <= 128) hipLaunchKernelGGL((conv1x1_stream_kernel<64, true>), grid, dim3(GEMM_THREADS), 0, st, a);
   else if (Ci <= 64) hipLaunchKernelGGL(conv1x1_stream_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);

@@ -6,7 +6,13 @@
 
 namespace hfta {
 int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
-                       const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st);
+                       const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st,
+                       float* stat_part = nullptr);
+// BatchNorm forward whose statistics come from per-slice partial sums (bn.hip)
+int bn_fwd_from_partials(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
+                         const float* beta, float eps, float momentum, float* running_mean, float* running_var,
+                         float* save_mean, float* save_invstd, void* Y, const int64_t ys[4], int act, float slope,
+                         const float* part, int parts, const void* shift, hipStream_t st);
 }
 
 using namespace hfta;
@@ -441,6 +447,42 @@ int hfta_conv1x1_fwd_sample_bias(int B, int Nb, int Ci, int Co, int L, int dtype
   d.bias = S; d.bias_mode = 1; d.bias_g0 = ss[0]; d.bias_g1 = ss[1];
   d.act = act; d.slope = act_slope;
   return gemm_launch(d, as_stream(stream));
+}
+
+// Conv1d k=1 + training-mode BatchNorm + activation.  When the streaming kernel takes the layer, its
+// epilogue leaves per-slice sums of the stored values in the workspace and the BatchNorm reads Z
+// once (normalisation only); otherwise the two operators run one after the other.
+size_t hfta_conv1x1_bn_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  if (check_conv1x1(B, Nb, Ci, Co, L, dtype) != HFTA_OK || dtype != HFTA_BF16) return 0;
+  return (size_t)B * Nb * ((L + 127) / 128) * Co * 2 * sizeof(float);
+}
+
+int hfta_conv1x1_bn_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                        const void* W, const void* bias, const float* gamma, const float* beta, float eps,
+                        float momentum, float* running_mean, float* running_var, float* save_mean,
+                        float* save_invstd, void* Z, const int64_t zs[4], void* Y, const int64_t ys[4], int act,
+                        float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+  int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
+  if (rc != HFTA_OK) return rc;
+  if (!X || !W || !Z || !Y || !xs || !zs || !ys || !gamma || !beta || !save_mean || !save_invstd || !(eps >= 0.f))
+    return HFTA_EINVAL;
+  if ((running_mean == nullptr) != (running_var == nullptr)) return HFTA_EINVAL;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (xs[3] != 1 || zs[3] != 1 || ys[3] != 1) return HFTA_EUNSUPPORTED;
+  hipStream_t st = as_stream(stream);
+  const size_t need = hfta_conv1x1_bn_fwd_workspace_bytes(B, Nb, Ci, Co, L, dtype);
+  if (dtype == HFTA_BF16 && need && workspace && ws_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 8 == 0) {
+    float* part = reinterpret_cast<float*>(workspace);
+    rc = hfta::conv1x1_stream_fwd(B, Nb, Ci, Co, L, X, xs, W, bias, Z, zs, HFTA_ACT_NONE, 0.f, st, part);
+    if (rc == HFTA_OK)
+      rc = hfta::bn_fwd_from_partials(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var,
+                                      save_mean, save_invstd, Y, ys, act, act_slope, part, Nb * ((L + 127) / 128), bias, st);
+    if (rc != HFTA_EUNSUPPORTED) return rc;
+  }
+  rc = hfta_conv1x1_fwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, HFTA_ACT_NONE, 0.f, stream);
+  if (rc != HFTA_OK) return rc;
+  return hfta_bn_fwd(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
+                     save_invstd, Y, ys, act, act_slope, stream);
 }
 
 // The data gradient of a narrow layer (Co <= 128, or Co <= 256 under at least 512 inputs) is a k=1 convolution of dY with the transposed

@@ -256,6 +256,52 @@ def test_bn_conv_layout(hb, dtype, B, Nb, C, L, act):
     check(host(dB), rdb, f32_tol(dtype), "dbeta")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,Nb,Ci,Co,L,act,bias", [
+    (2, 3, 64, 64, 2500, 1, True),     # config 1's middle layers: streaming kernel, ragged last slice (2500 = 19 * 128 + 68)
+    (2, 2, 64, 128, 300, 2, True),     # single W tile of 128 rows
+    (1, 2, 128, 320, 260, 1, False),   # three W tiles (ragged: 320 = 2 * 128 + 64), 128-deep reduction, no conv bias
+    (2, 2, 24, 40, 100, 0, True),      # not the streaming kernel's shape: the two operators run one after the other
+])
+def test_conv1x1_bn_fwd(hb, dtype, B, Nb, Ci, Co, L, act, bias):
+    """Conv1d k=1 + training BatchNorm + activation in one call against the composition of the two
+    single operators of the oracle (z stored and rounded, statistics of the stored z)."""
+    print(f"conv1x1+bn {dtype} B={B} Nb={Nb} {Ci}->{Co} L={L} act={act} bias={bias}", flush=True)
+    x = hi.normal(301, (Nb, B * Ci, L), dtype)
+    w = hi.normal(302, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    b = (hi.normal(303, (B * Co,), dtype) * 2.0) if bias else None      # a large bias: the statistics are shifted by it
+    g = (hi.normal(304, (B * Co,)) * 0.5 + 1.0).astype(np.float32)
+    bt = hi.normal(305, (B * Co,)) * 0.3
+    rm, rv = hi.normal(306, (B * Co,)), np.abs(hi.normal(307, (B * Co,))) + 0.5
+    xs, zs = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    X, W, Bi = dev(x, dtype), dev(w, dtype), (dev(b, dtype) if bias else None)
+    G, Bt, RM, RV = dev(g), dev(bt), dev(rm), dev(rv)
+    SM, SI = empty((B * Co,), torch.float32), empty((B * Co,), torch.float32)
+    Z, Y = empty((Nb, B * Co, L), dtype), empty((Nb, B * Co, L), dtype)
+    nws = hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype])
+    ws = torch.empty(max(nws, 8), dtype=torch.uint8, device="cuda")
+    hb.conv1x1_bn_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Bi, G, Bt, 1e-5, 0.1, RM, RV, SM, SI, Z, zs, Y, zs, act, 0.2, ws)
+    rz = oa.conv1x1_fwd(B, x, w, b)
+    check(host(Z), rz, TOL[dtype], "Z")
+    # the BatchNorm is checked on the bits the device stored for Z (what its statistics are taken from)
+    zdev = host(Z).astype(np.float64)
+    ry, rmean, rinv, nrm, nrv = oa.bn_fwd(B, zdev, g, bt, 1e-5, 0.1, rm, rv)
+    oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
+    check(host(Y), oops.act_fwd(ry, oact, 0.2), TOL[dtype], "Y")
+    check(host(SM), rmean, 1e-5, "mean")
+    check(host(SI), rinv, 1e-5, "invstd")
+    check(host(RM), nrm, 1e-5, "running_mean")
+    check(host(RV), nrv, 1e-5, "running_var")
+    # and the same call without a workspace (the two-operator path) agrees
+    Z2, Y2 = empty((Nb, B * Co, L), dtype), empty((Nb, B * Co, L), dtype)
+    SM2, SI2 = empty((B * Co,), torch.float32), empty((B * Co,), torch.float32)
+    hb.conv1x1_bn_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Bi, G, Bt, 1e-5, 0.1, None, None, SM2, SI2, Z2, zs, Y2, zs, act, 0.2, None)
+    assert np.array_equal(host(Z2), host(Z)), "Z differs between the two paths"
+    check(host(SM2), host(SM), 1e-5, "mean (two-operator path)")
+    check(host(SI2), host(SI), 1e-5, "invstd (two-operator path)")
+    check(host(Y2), host(Y), TOL[dtype], "Y (two-operator path)")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("Nb", [32, 5, 64, 100])      # up to 64 samples: the column-in-registers kernels
 def test_bn_linear_layout_and_independence(hb, dtype, Nb):
