@@ -19,6 +19,8 @@ namespace hfta {
 // beats the k-loop GEMM only when many W tiles share one X tile.
 constexpr int STREAM_WIDE_MIN_CO = 512;
 
+typedef __bf16 stat_bf16x2 __attribute__((ext_vector_type(2)));   // operand of the two-element dot product
+
 struct StreamArgs {
   const bf16_raw* W;
   const bf16_raw* X;
@@ -155,24 +157,27 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
     store_tile<bf16_raw, bf16_raw, false>(acc, Ws, Yb, p.y_ld, p.Co, p.L, ct * 128, l0, bias, 1, p.act, p.slope, p.c_vec, t);
     if (p.stat_part) {
       // the staged tile [128 channels][128 points] is still in LDS: two threads per channel add their
-      // 64 points (rounded values, shifted by the channel's bias so that fp32 keeps its accuracy)
+      // 64 points with two-element dot products (sum of z and of z^2 of the rounded values), then
+      // move both sums to the channel's bias as origin, the form the partial sums are kept in.  A
+      // point past the slice's end holds the bias itself (its X column was read as zeros), i.e. it
+      // adds nothing to the shifted sums, so all 64 columns count.
       const int row = t >> 1, half = t & 1;
       const int m = ct * 128 + row;
       const float shift = (bias && m < p.Co) ? bf16_to_f32(bias[m]) : 0.f;
       const unsigned char* src = Ws + row * EPI_PITCH2 + half * 128;
+      const stat_bf16x2 ones = __builtin_bit_cast(stat_bf16x2, 0x3f803f80u);
       float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const uint2 v = *reinterpret_cast<const uint2*>(src + q * 8);
-        const float z[4] = {__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
-                            __uint_as_float(v.y & 0xffff0000u)};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float d = (l0 + half * 64 + q * 4 + e < p.L) ? z[e] - shift : 0.f;
-          s1 += d;
-          s2 = fmaf(d, d, s2);
-        }
+        const stat_bf16x2 lo = __builtin_bit_cast(stat_bf16x2, v.x), hi = __builtin_bit_cast(stat_bf16x2, v.y);
+        s1 = __builtin_amdgcn_fdot2_f32_bf16(lo, ones, s1, false);
+        s2 = __builtin_amdgcn_fdot2_f32_bf16(lo, lo, s2, false);
+        s1 = __builtin_amdgcn_fdot2_f32_bf16(hi, ones, s1, false);
+        s2 = __builtin_amdgcn_fdot2_f32_bf16(hi, hi, s2, false);
       }
+      s2 = fmaf(shift, fmaf(64.f, shift, -2.f * s1), s2);      // sum (z - c)^2 = sum z^2 - 2 c sum z + 64 c^2
+      s1 = fmaf(-64.f, shift, s1);
       s1 += __shfl_xor(s1, 1, 64);
       s2 += __shfl_xor(s2, 1, 64);
       if (half == 0 && m < p.Co)
