@@ -184,6 +184,38 @@ int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                      void* dX, const int64_t dxs[4], float* dW, float* dbias,
                      void* workspace, size_t ws_bytes, void* stream);
 
+/* Backward of the block hfta_conv1x1_bn_fwd computes (rows "Conv1d" and "BatchNorm1d" of the fusion
+ * rules table), BatchNorm backward and convolution backward in one call:
+ *   g  = dY * act'(gamma xhat + beta),  xhat = (Z - mean) invstd        (dY: gradient at the block's output Y)
+ *   dZ = gamma invstd (g - mean_{n,l}(g) - xhat mean_{n,l}(g xhat)),  rounded to the storage dtype
+ *   dgamma[b,c] = sum g xhat,  dbeta[b,c] = sum g                       (fp32)
+ *   dX, dW as hfta_conv1x1_bwd with dZ as its dY;  dbias[b,o] = sum_{n,l} dZ   (fp32, NULL = skip)
+ * i.e. the results of hfta_bn_bwd followed by hfta_conv1x1_bwd with dZ stored in between, up to the
+ * fp32 summation order.  X, Z, dY, dX: logical [B][Nb][C][L] with strides, stride_l == 1; W as in
+ * hfta_conv1x1_fwd (may be NULL when dX is NULL); gamma, beta, save_mean, save_invstd: [B][Co] fp32
+ * as hfta_bn_fwd left them.  dX == NULL skips the data gradient (a network's first layer); dX must
+ * not overlap X, Z or dY (it is written while other slices of those are still being read).
+ * bf16 layers with Ci <= 128, Co <= 128, L % 4 == 0, 8-byte aligned X, Z, dY (and dX) and strides
+ * that are multiples of 4 elements run as one
+ * reduction kernel (dgamma, dbeta and per-channel constants) plus ONE streaming kernel that forms
+ * dZ per 128-point slice in registers and feeds it to both products from LDS: dZ never goes to
+ * device memory.  The workspace (hfta_conv1x1_bn_bwd_workspace_bytes, 256-byte aligned) then holds
+ * the constants and the per-workgroup fp32 partials of dW and dbias, added in a fixed order
+ * (bit-reproducible).  Every other shape or dtype runs the two single operators with dZ in the
+ * workspace (the query returns that larger size for them).  A shape the streaming kernel takes
+ * whose pointers or strides break its alignment rules needs the larger workspace as well:
+ * HFTA_EWORKSPACE if it is not there.  Nothing is allocated.
+ * hfta_conv1x1_bn_bwd_one_pass returns 1 for the shapes and dtype of the one-kernel form, else 0 (a
+ * caller that already owns a dZ-sized buffer may prefer the two single operators for the others). */
+int hfta_conv1x1_bn_bwd_one_pass(int B, int Nb, int Ci, int Co, int L, int dtype);
+size_t hfta_conv1x1_bn_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
+int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                        const void* X, const int64_t xs[4], const void* W,
+                        const void* Z, const int64_t zs[4], const void* dY, const int64_t dys[4],
+                        const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
+                        void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
+                        int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * Fused Conv2d (row "Conv2d" -> grouped Conv2d with G = B; g = 1 per model).
  *   X:[Nb][B*Ci][H][W]  Wt:[B*Co][Ci][kh][kw]  bias:[B*Co] or NULL

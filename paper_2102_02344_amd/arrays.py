@@ -28,6 +28,13 @@ def _cs(B, C, L):
     return (C * L, B * C * L, L, 1)
 
 
+def _bn_bwd_one_pass(B, Nb, ci, co, L, dt):
+    """True when ``conv1x1_bn_bwd`` runs this layer as one streaming kernel (dz never stored).  Layers it
+    would run as the two single operators are called as such here, with dz in one of the array's
+    gradient buffers instead of a workspace of that size."""
+    return hb.conv1x1_bn_bwd_one_pass(B, Nb, ci, co, L, dt)
+
+
 class ParamArena:
     """Parameter-major storage of B models' parameters, gradients and Adam state.
 
@@ -222,9 +229,15 @@ class FusedPointNetCls(ParamArena):
         self.fd = [torch.empty(B * Nb * fmax, **act) for _ in range(2)]
         self.loss = torch.empty(B, **f32)
         ws = 4
+        self.one_pass = [_bn_bwd_one_pass(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt) for i in range(self.nconv)]
         for i in range(self.nconv):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt),
                      hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
+            if i < self.nconv - 1:
+                if i in self.unfused:
+                    ws = max(ws, hb.conv1x1_bn_bwd_workspace_bytes(1, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
+                elif self.one_pass[i]:
+                    ws = max(ws, hb.conv1x1_bn_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nfc):
             ws = max(ws, hb.linear_bwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt),
                      hb.linear_fwd_workspace_bytes(B, Nb, spec.fc[i], spec.fc[i + 1], self.dt))
@@ -400,14 +413,27 @@ class FusedPointNetCls(ParamArena):
                   dbt=self.g(k + ".bn.b"))
                 da = dxin
                 continue
-            dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
-            if i in self.unfused and i < self.nconv - 1:
-                xin = self.points if i == 0 else self.a[i - 1]
-                dxin = None if i == 0 else self.dbuf[cur][:Nb * B * ci * L]
-                self._layer_bwd_unfused(i, xin, ci, co, da, dz, dxin)
-                da = dxin
+            xin = self.points if i == 0 else self.a[i - 1]
+            if i < self.nconv - 1 and (i in self.unfused or self.one_pass[i]):
+                # BatchNorm backward + convolution backward in one call: dz stays on chip.  The data
+                # gradient goes to the other buffer (dY is still being read while it is written).
+                dxin = None if i == 0 else self.dbuf[cur ^ 1][:Nb * B * ci * L]
+                if i in self.unfused:
+                    self._layer_bwd_unfused(i, xin, ci, co, da, dxin)
+                else:
+                    hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), self.z[i], cs, da, cs,
+                                      self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],
+                                      self.saved[k + ".bn.invstd"], dxin, None if i == 0 else _cs(B, ci, L),
+                                      self.g(k + ".w"), self.g(k + ".b"), self.g(k + ".bn.g"), self.g(k + ".bn.b"),
+                                      hb.ACT_RELU, 0.0, self.ws)
+                    P("conv1x1_bn_bwd", layer=k, x=xin, w=self.w(k + ".w"), z=self.z[i], dy=da.view(Nb, B * co, L),
+                      g=self.master(k + ".bn.g"), bt=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"],
+                      invstd=self.saved[k + ".bn.invstd"], dx=None if i == 0 else dxin.view(Nb, B * ci, L),
+                      dw=self.g(k + ".w"), db=self.g(k + ".b"), dg=self.g(k + ".bn.g"), dbt=self.g(k + ".bn.b"))
+                da, cur = dxin, cur ^ 1
                 continue
-            if i == self.nconv - 1:
+            dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
+            if i == self.nconv - 1:     # BatchNorm backward through the max over points
                 hb.bn_bwd_maxpool(B, Nb, co, L, dt, self.z[i], cs, dpool, self.pool_idx, (Nb * co, co, 1),
                                   self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],
                                   self.saved[k + ".bn.invstd"], dz, cs, self.g(k + ".bn.g"), self.g(k + ".bn.b"),
@@ -424,7 +450,6 @@ class FusedPointNetCls(ParamArena):
                   g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"],
                   invstd=self.saved[k + ".bn.invstd"], dx=dz.view(Nb, B * co, L), dg=self.g(k + ".bn.g"),
                   db=self.g(k + ".bn.b"))
-            xin = self.points if i == 0 else self.a[i - 1]
             dxin = None if i == 0 else self.dbuf[cur][:Nb * B * ci * L]
             # data gradient and weight gradient as two calls: one GEMM launch each (plus the weight
             # gradient's split-K reduction), so a caller can time them separately
@@ -457,21 +482,17 @@ def _unfused_methods():
                               _off(self.saved[k + ".bn.mean"], b * co), _off(self.saved[k + ".bn.invstd"], b * co),
                               _off(self.z[i], b * co * L), cs, _off(self.a[i], b * co * L), cs, hb.ACT_RELU, 0.0, self.ws)
 
-    def _layer_bwd_unfused(self, i, xin, ci, co, da, dz, dxin):
+    def _layer_bwd_unfused(self, i, xin, ci, co, da, dxin):
         B, Nb, L, dt, k = self.B, self.Nb, self.L, self.dt, f"conv{i}"
         xs, cs = _cs(B, ci, L), _cs(B, co, L)
-        for b in range(B):
-            hb.bn_bwd(1, Nb, co, L, dt, _off(self.z[i], b * co * L), cs, _off(da, b * co * L), cs,
-                      _off(self.master(k + ".bn.g"), b * co), _off(self.master(k + ".bn.b"), b * co),
-                      _off(self.saved[k + ".bn.mean"], b * co), _off(self.saved[k + ".bn.invstd"], b * co),
-                      _off(dz, b * co * L), cs, _off(self.g(k + ".bn.g"), b * co), _off(self.g(k + ".bn.b"), b * co),
-                      hb.ACT_RELU, 0.0, _off(self.g(k + ".b"), b * co))
-        for b in range(B):      # only now: dxin shares its buffer with da, which every model's BatchNorm has read
-            if dxin is not None:
-                hb.conv1x1_bwd(1, Nb, ci, co, L, dt, None, None, _off(self.w(k + ".w"), b * co * ci), _off(dz, b * co * L),
-                               cs, _off(dxin, b * ci * L), xs, None, None, self.ws)
-            hb.conv1x1_bwd(1, Nb, ci, co, L, dt, _off(xin, b * ci * L), xs, None, _off(dz, b * co * L), cs, None, None,
-                           _off(self.g(k + ".w"), b * co * ci), None, self.ws)
+        for b in range(B):      # the same operator as the fused array's, one model at a time
+            hb.conv1x1_bn_bwd(1, Nb, ci, co, L, dt, _off(xin, b * ci * L), xs, _off(self.w(k + ".w"), b * co * ci),
+                              _off(self.z[i], b * co * L), cs, _off(da, b * co * L), cs,
+                              _off(self.master(k + ".bn.g"), b * co), _off(self.master(k + ".bn.b"), b * co),
+                              _off(self.saved[k + ".bn.mean"], b * co), _off(self.saved[k + ".bn.invstd"], b * co),
+                              None if dxin is None else _off(dxin, b * ci * L), None if dxin is None else xs,
+                              _off(self.g(k + ".w"), b * co * ci), _off(self.g(k + ".b"), b * co),
+                              _off(self.g(k + ".bn.g"), b * co), _off(self.g(k + ".bn.b"), b * co), hb.ACT_RELU, 0.0, self.ws)
 
     FusedPointNetCls._layer_fwd_unfused = _layer_fwd_unfused
     FusedPointNetCls._layer_bwd_unfused = _layer_bwd_unfused
@@ -914,9 +935,12 @@ class FusedPointNetSeg(ParamArena):
         self.loss = torch.empty(B, **f32)
         ws = max(4, hb.softmax_xent_points_workspace_bytes(B, Nb, L), hb.linear_bwd_workspace_bytes(B, Nb, Cg, H[1], self.dt),
                  hb.linear_fwd_workspace_bytes(B, Nb, Cg, H[1], self.dt))
+        self.one_pass = [_bn_bwd_one_pass(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt) for i in range(self.nconv)]
         for i in range(self.nconv):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt),
                      hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
+            if self.one_pass[i]:
+                ws = max(ws, hb.conv1x1_bn_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
         for i in range(self.nh):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, Cp if i == 0 else H[i], H[i + 1], L, self.dt),
                      hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, Cp if i == 0 else H[i], H[i + 1], L, self.dt))
@@ -1046,6 +1070,20 @@ class FusedPointNetSeg(ParamArena):
                 hb.add_strided(B, Nb, co, L, dt, dnext, cs, sl, cst, dsum, cs)
                 P("add_strided", a=dnext.view(Nb, B * co, L), b=slv, y=dsum.view(Nb, B * co, L))
                 da, das, dav = dsum, cs, dsum.view(Nb, B * co, L)
+            if self.one_pass[i]:
+                # BatchNorm backward + convolution backward in one call (dz stays on chip)
+                if i > 0:
+                    xin, xs, xinv = self._slice(self.cat, i - 1)[0], cst, self._slice(self.cat, i - 1)[1]
+                    dnext = self.dbuf[1][:Nb * B * ci * L]
+                else:
+                    xin, xs, xinv, dnext = self.points, _cs(B, 3, L), self.points, None
+                hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, xs, self.w(k + ".w"), self.z[i], cs, da, das, *bn(k), *st(k),
+                                  dnext, None if i == 0 else _cs(B, ci, L), self.g(k + ".w"), self.g(k + ".b"),
+                                  self.g(k + ".bn.g"), self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.ws)
+                P("conv1x1_bn_bwd", layer=k, x=xinv, w=self.w(k + ".w"), z=self.z[i], dy=dav, g=bn(k)[0], bt=bn(k)[1],
+                  mean=st(k)[0], invstd=st(k)[1], dx=None if i == 0 else dnext.view(Nb, B * ci, L), dw=self.g(k + ".w"),
+                  db=self.g(k + ".b"), dg=self.g(k + ".bn.g"), dbt=self.g(k + ".bn.b"))
+                continue
             dz = self.dbuf[0][:Nb * B * co * L]
             hb.bn_bwd(B, Nb, co, L, dt, self.z[i], cs, da, das, *bn(k), *st(k), dz, cs, self.g(k + ".bn.g"),
                       self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.g(k + ".b"))
@@ -1217,9 +1255,12 @@ class _PointChain:
         self.a = [torch.empty(Nb, B * c, L, **act) for c in self.conv[1:1 + na]]
         cmax = max(self.conv)
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
+        self.one_pass = [_bn_bwd_one_pass(B, Nb, self.conv[i], self.conv[i + 1], L, dt) for i in range(self.nconv)]
         for i in range(self.nconv):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt),
                      hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt))
+            if self.one_pass[i]:
+                ws = max(ws, hb.conv1x1_bn_bwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt))
         if self.head:
             Cp = self.conv[-1]
             self.pooled = torch.empty(B, Nb, Cp, **act)
@@ -1318,24 +1359,32 @@ class _PointChain:
             hb.linear_bwd(B, Nb, fx, fy, dt, hin, A.w(k + ".w"), d, nd, A.g(k + ".w"), own_db, ws)
             d, cur = nd, cur ^ 1
 
-        da, cur = d, 0
+        da, cur = d, 0      # da never lives in dbuf[cur]
         for i in reversed(range(self.nconv)):
             ci, co, k = self.conv[i], self.conv[i + 1], f"{self.px}conv{self.cb + i}"
             cs, xs = _cs(B, co, L), _cs(B, ci, L)
             xin = self.x_in if i == 0 else self.a[i - 1]
             need_dx = i > 0 or want_dx
-            dxin = self.dbuf[cur][:Nb * B * ci * L] if need_dx else None
             tail = self.head and i == self.nconv - 1
             bn = (A.master(k + ".bn.g"), A.master(k + ".bn.b"), A.saved[k + ".bn.mean"], A.saved[k + ".bn.invstd"])
             if tail and self.fused_tail:
                 # the operator always writes dX: give it a buffer even when nobody reads it
-                dxo = dxin if need_dx else self.dbuf[cur][:Nb * B * ci * L]
+                dxo = self.dbuf[cur][:Nb * B * ci * L]
                 hb.conv1x1_bn_maxpool_bwd(B, Nb, ci, co, L, dt, xin, xs, A.w(k + ".w"), A.w(k + ".b"), None, None, self.zhit,
                                           self.moments, da, self.pool_idx, (Nb * co, co, 1), *bn, dxo, xs, A.g(k + ".w"),
                                           A.g(k + ".b"), A.g(k + ".bn.g"), A.g(k + ".bn.b"), hb.ACT_RELU, 0.0, ws)
-                da = dxin
+                da, cur = (dxo if need_dx else None), cur ^ 1
                 continue
-            dz = self.dbuf[cur ^ 1][:Nb * B * co * L]
+            if not tail and self.one_pass[i]:
+                # BatchNorm backward + convolution backward in one call; its dX must not share da's buffer
+                dxin = self.dbuf[cur][:Nb * B * ci * L] if need_dx else None
+                hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, xs, A.w(k + ".w"), self.z[i], cs, da, cs, *bn, dxin,
+                                  xs if need_dx else None, A.g(k + ".w"), A.g(k + ".b"), A.g(k + ".bn.g"), A.g(k + ".bn.b"),
+                                  hb.ACT_RELU, 0.0, ws)
+                da, cur = dxin, cur ^ 1
+                continue
+            dz = self.dbuf[cur][:Nb * B * co * L]
+            dxin = self.dbuf[cur ^ 1][:Nb * B * ci * L] if need_dx else None       # over da, which the BatchNorm has consumed
             if tail:
                 hb.bn_bwd_maxpool(B, Nb, co, L, dt, self.z[i], cs, da, self.pool_idx, (Nb * co, co, 1), *bn, dz, cs,
                                   A.g(k + ".bn.g"), A.g(k + ".bn.b"), hb.ACT_RELU, 0.0, A.g(k + ".b"))

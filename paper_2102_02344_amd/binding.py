@@ -53,6 +53,10 @@ _SIGS = {
     "hfta_conv1x1_bn_fwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bn_fwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _p, _f, _f, _p, _p, _p, _p, _p, _s4, _p, _s4,
                                  _i, _f, _p, _sz, _p]),
+    "hfta_conv1x1_bn_bwd_one_pass": (_i, [_i, _i, _i, _i, _i, _i]),
+    "hfta_conv1x1_bn_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
+    "hfta_conv1x1_bn_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _p,
+                                 _i, _f, _p, _sz, _p]),
     "hfta_conv1x1_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _p, _p, _p, _sz, _p]),
     "hfta_conv2d_grouped_fwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _i, _f, _p, _sz, _p]),
@@ -215,6 +219,23 @@ def conv1x1_bn_fwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, gamma, beta, eps, mo
                                     _ptr(beta), eps, momentum, _ptr(running_mean), _ptr(running_var), _ptr(save_mean),
                                     _ptr(save_invstd), _ptr(Z), _strides(zs), _ptr(Y), _strides(ys), act, act_slope,
                                     wp, wb, _stream(stream)), "hfta_conv1x1_bn_fwd")
+
+
+def conv1x1_bn_bwd_one_pass(B, Nb, Ci, Co, L, dtype) -> bool:
+    return bool(_lib.hfta_conv1x1_bn_bwd_one_pass(B, Nb, Ci, Co, L, dtype))
+
+
+def conv1x1_bn_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype) -> int:
+    return _lib.hfta_conv1x1_bn_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype)
+
+
+def conv1x1_bn_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd, dX, dxs, dW,
+                   dbias, dgamma, dbeta, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_conv1x1_bn_bwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(Z), _strides(zs),
+                                    _ptr(dY), _strides(dys), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd),
+                                    _ptr(dX), _strides(dxs), _ptr(dW), _ptr(dbias), _ptr(dgamma), _ptr(dbeta), act,
+                                    act_slope, wp, wb, _stream(stream)), "hfta_conv1x1_bn_bwd")
 
 
 def conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype) -> int:

@@ -276,6 +276,51 @@ __global__ __launch_bounds__(NT) void bn_bwd_conv_kernel(BnBwdArgs p) {
   }
 }
 
+// The reduction half of the backward pass alone: dbeta, dgamma, and per channel the eight constants
+// a consumer needs to form dX = sc * (g - mb - xhat * mg) by itself while it streams x and dY:
+// coef[k] = {mean, invstd, gamma, beta, mb, mg, sc, 0}.  Nothing of size [Nb, C, L] is written.
+template <typename T, int VEC, int NT>
+__global__ __launch_bounds__(NT) void bn_bwd_conv_coef_kernel(BnBwdArgs p, float* __restrict__ coef) {
+  __shared__ float sh[NT / 64][2];
+  const int c = blockIdx.x, b = blockIdx.y, k = b * p.C + c;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
+  const T* dy = reinterpret_cast<const T*>(p.dY) + b * p.dysb + c * p.dysc;
+  const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
+  const int chunks = p.L / VEC;
+  float s1 = 0.f, s2 = 0.f;
+  for (RowWalk w(chunks, NT); w.n < p.Nb;) {
+    float v[BN_UNROLL][VEC], d[BN_UNROLL][VEC];
+    bool ok[BN_UNROLL];
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u) {
+      ok[u] = w.n < p.Nb;
+      load_vec<T, VEC>(ok[u] ? x + w.n * p.xsn + w.ch * VEC : x, v[u]);
+      load_vec<T, VEC>(ok[u] ? dy + w.n * p.dysn + w.ch * VEC : dy, d[u]);
+      w.step();
+    }
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u)
+      if (ok[u]) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float xh = (v[u][e] - mean) * invstd;
+          const float gr = d[u][e] * act_grad(fmaf(g, xh, bt), p.act, p.slope);
+          s1 += gr;
+          s2 = fmaf(gr, xh, s2);
+        }
+      }
+  }
+  block_sum2<NT / 64>(s1, s2, sh);
+  if (threadIdx.x == 0) {
+    p.dbeta[k] = s1;
+    p.dgamma[k] = s2;
+    const float m = (float)p.Nb * (float)p.L;
+    float4* o = reinterpret_cast<float4*>(coef + (int64_t)k * 8);
+    o[0] = make_float4(mean, invstd, g, bt);
+    o[1] = make_float4(s1 / m, s2 / m, g * invstd, 0.f);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(BNL_C * BNL_N) void bn_bwd_linear_kernel(BnBwdArgs p) {
   __shared__ float red[BNL_N][BNL_C];
@@ -389,6 +434,26 @@ int bn_fwd_from_partials(int B, int Nb, int C, int L, int dtype, const void* X, 
             else hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 4, 256>), grid, dim3(256), 0, st, a, part, parts, sv); }
   else { if (big) hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 1, 1024>), grid, dim3(1024), 0, st, a, part, parts, sv);
          else hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 1, 256>), grid, dim3(256), 0, st, a, part, parts, sv); }
+  return launch_status();
+}
+
+// Reduction half of the training backward pass over the [Nb, B*C, L] layout: dgamma, dbeta and the
+// per-channel constants (eight floats, see the kernel) for a consumer that applies them itself.
+int bn_bwd_coef(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const void* dY,
+                const int64_t dys[4], const float* gamma, const float* beta, const float* save_mean,
+                const float* save_invstd, float* dgamma, float* dbeta, float* coef, int act, float slope, hipStream_t st) {
+  if (B > 65535 || layout_kind(xs, L) != 1 || layout_kind(dys, L) != 1) return HFTA_EUNSUPPORTED;
+  BnBwdArgs a{X, dY, nullptr, gamma, beta, save_mean, save_invstd, dgamma, dbeta, nullptr,
+              xs[0], xs[1], xs[2], dys[0], dys[1], dys[2], 0, 0, 0, Nb, C, L, act, slope};
+  const dim3 grid((unsigned)C, (unsigned)B);
+  const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(dY, dys, L, dtype);
+  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
+#define HFTA_BN_COEF(T, V) \
+  do { if (big) hipLaunchKernelGGL((bn_bwd_conv_coef_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a, coef); \
+       else hipLaunchKernelGGL((bn_bwd_conv_coef_kernel<T, V, 256>), grid, dim3(256), 0, st, a, coef); } while (0)
+  if (dtype == HFTA_BF16) { if (v4) HFTA_BN_COEF(bf16_raw, 4); else HFTA_BN_COEF(bf16_raw, 1); }
+  else { if (v4) HFTA_BN_COEF(float, 4); else HFTA_BN_COEF(float, 1); }
+#undef HFTA_BN_COEF
   return launch_status();
 }
 }  // namespace hfta

@@ -13,6 +13,13 @@ int bn_fwd_from_partials(int B, int Nb, int C, int L, int dtype, const void* X, 
                          const float* beta, float eps, float momentum, float* running_mean, float* running_var,
                          float* save_mean, float* save_invstd, void* Y, const int64_t ys[4], int act, float slope,
                          const float* part, int parts, const void* shift, hipStream_t st);
+bool conv1x1_bn_bwd_streams(int B, int Ci, int Co, int L, int dtype);
+size_t conv1x1_bn_bwd_stream_bytes(int B, int Nb, int Ci, int Co, int L);
+int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
+                          const void* Z, const int64_t zs[4], const void* dY, const int64_t dys[4], const float* gamma,
+                          const float* beta, const float* save_mean, const float* save_invstd, void* dX,
+                          const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act, float slope,
+                          void* workspace, hipStream_t st);
 }
 
 using namespace hfta;
@@ -556,6 +563,55 @@ int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
     return launch_status();
   }
   return HFTA_OK;
+}
+
+
+// BatchNorm backward + k=1 convolution backward in one call.  Shapes the one-pass kernel takes need
+// its constants and partials only; every other case runs the two single operators with dz in the
+// workspace: [dz, 256-byte aligned size][the convolution backward's own workspace].
+static size_t cbb_fallback_dz_bytes(int B, int Nb, int Co, int L, int dtype) {
+  return wt_offset((size_t)B * Nb * Co * L * dtype_size(dtype));
+}
+
+int hfta_conv1x1_bn_bwd_one_pass(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  return check_conv1x1(B, Nb, Ci, Co, L, dtype) == HFTA_OK && hfta::conv1x1_bn_bwd_streams(B, Ci, Co, L, dtype) ? 1 : 0;
+}
+
+size_t hfta_conv1x1_bn_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  if (check_conv1x1(B, Nb, Ci, Co, L, dtype) != HFTA_OK) return 0;
+  if (hfta::conv1x1_bn_bwd_streams(B, Ci, Co, L, dtype)) return hfta::conv1x1_bn_bwd_stream_bytes(B, Nb, Ci, Co, L);
+  return cbb_fallback_dz_bytes(B, Nb, Co, L, dtype) + hfta_conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype);
+}
+
+int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                        const void* W, const void* Z, const int64_t zs[4], const void* dY, const int64_t dys[4],
+                        const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
+                        void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act,
+                        float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+  int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
+  if (rc != HFTA_OK) return rc;
+  if (!X || !xs || !Z || !zs || !dY || !dys || !gamma || !beta || !save_mean || !save_invstd || !dW || !dgamma || !dbeta)
+    return HFTA_EINVAL;
+  if (dX && (!W || !dxs)) return HFTA_EINVAL;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (xs[3] != 1 || zs[3] != 1 || dys[3] != 1 || (dX && dxs[3] != 1)) return HFTA_EUNSUPPORTED;
+  hipStream_t st = as_stream(stream);
+  if (hfta::conv1x1_bn_bwd_streams(B, Ci, Co, L, dtype)) {
+    if (!workspace || ws_bytes < hfta::conv1x1_bn_bwd_stream_bytes(B, Nb, Ci, Co, L)) return HFTA_EWORKSPACE;
+    rc = hfta::conv1x1_bn_bwd_stream(B, Nb, Ci, Co, L, X, xs, W, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd,
+                                     dX, dxs, dW, dbias, dgamma, dbeta, act, act_slope, workspace, st);
+    if (rc != HFTA_EUNSUPPORTED) return rc;
+  }
+  const size_t dzb = cbb_fallback_dz_bytes(B, Nb, Co, L, dtype);
+  const size_t need = dzb + hfta_conv1x1_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype);
+  if (!workspace || ws_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return HFTA_EWORKSPACE;
+  const int64_t ds[4] = {(int64_t)Co * L, (int64_t)B * Co * L, L, 1};
+  float* sink = nullptr;
+  rc = hfta_bn_bwd(B, Nb, Co, L, dtype, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd, workspace, ds, dgamma, dbeta,
+                   dbias ? dbias : sink, act, act_slope, stream);
+  if (rc != HFTA_OK) return rc;
+  unsigned char* rest = reinterpret_cast<unsigned char*>(workspace) + dzb;
+  return hfta_conv1x1_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, workspace, ds, dX, dxs, dW, nullptr, rest, ws_bytes - dzb, stream);
 }
 
 }  // extern "C"

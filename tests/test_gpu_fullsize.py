@@ -10,7 +10,7 @@ import torch
 
 import hfta_inputs as hi
 from oracle import ops as oops
-from util import DT, TOL, check_tail_argmax
+from util import DT, TOL, bn_preact_fp32, check_tail_argmax
 
 pytestmark = pytest.mark.gpu
 bf = torch.bfloat16
@@ -97,6 +97,41 @@ def test_c1_full_size_step_sampled(fused_tail):
                 assert abs(float(kw["dg"][k]) - dg[0]) <= 2e-4 * max(abs(dg[0]), 1e-2 * sc)
                 assert abs(float(kw["db"][k]) - dbt[0]) <= 2e-4 * max(abs(dbt[0]), 1e-2 * sc)
             seen.append(op)
+        elif op == "conv1x1_bn_bwd" and lay in ("conv0", "conv2", "conv3"):
+            # BatchNorm backward + convolution backward in one call (3 -> 64 without a data gradient,
+            # 64 -> 64, 64 -> 128): ONE seeded model of the eight in full, every output, against the
+            # oracle's chain of the two single operators with dz stored in between (the models of an
+            # array share nothing, so the oracle runs that model alone on the bits the GPU read)
+            print("full-size check", op, lay, flush=True)
+            b = int(rng.integers(0, B))
+            Co = kw["z"].shape[1] // B
+            Ci = kw["x"].shape[1] // B
+            so, si = slice(b * Co, (b + 1) * Co), slice(b * Ci, (b + 1) * Ci)
+            z, dy, x = f64(kw["z"][:, so, :]), f64(kw["dy"][:, so, :]), f64(kw["x"][:, si, :])
+            g, bt_, mean, invstd = (f64(kw[n_])[so] for n_ in ("g", "bt", "mean", "invstd"))
+            w = f64(kw["w"].view(B, Co, Ci)[b])
+            dz, dg, dbt = oops.bn_bwd(z, oops.act_bwd(bn_preact_fp32(z, g, bt_, mean, invstd), dy, oops.ACT_RELU), g, mean, invstd)
+            sc = np.abs(dy).sum(axis=(0, 2))
+            assert np.all(np.abs(f64(kw["dg"])[so] - dg) <= 2e-4 * np.maximum(np.abs(dg), 1e-2 * sc)), f"{lay} dgamma"
+            assert np.all(np.abs(f64(kw["dbt"])[so] - dbt) <= 2e-4 * np.maximum(np.abs(dbt), 1e-2 * sc)), f"{lay} dbeta"
+            dzs = oops.store(dz, "bf16")
+            dx, dw, db = oops.conv1x1_bwd(x, w, dzs)
+            if kw["dx"] is not None:
+                rel_ok(f64(kw["dx"][:, si, :]), dx, tol, f"{lay} dX")
+            # dz rounds the other way for a few elements in a thousand (fp32 against float64 arithmetic),
+            # each moving one term of a weight-gradient element by one bf16 ulp (2^-8 of the term).  The
+            # flips are not independent: behind a ReLU that is off, dz = -sc (mb + xhat mg) takes one value
+            # per distinct stored z, so all points of a channel that share a z value flip together.  Worst
+            # case (every term flips) is 2^-8 of the sum of magnitudes; the bound here is 1e-4 of it (or 1e-2
+            # of the element itself), and 3e-4 in root mean square over the layer's weight gradient.
+            gw = f64(kw["dw"].view(B, Co, Ci)[b])
+            terms = np.einsum("nol,ncl->oc", np.abs(dzs), np.abs(x))
+            ratio = np.abs(gw - dw) / np.maximum(np.abs(dw), 1e-2 * terms)
+            assert ratio.max() <= 1e-2, f"{lay} dW: worst {ratio.max():.3e} at {np.unravel_index(ratio.argmax(), ratio.shape)}, " \
+                                        f"{(ratio > 1e-2).sum()} of {ratio.size} beyond"
+            assert np.sqrt(np.mean((gw - dw) ** 2)) <= 3e-4 * np.sqrt(np.mean(dw ** 2)), f"{lay} dW (rms)"
+            assert np.all(np.abs(f64(kw["db"])[so] - db) <= 2e-4 * np.abs(dzs).sum(axis=(0, 2))), f"{lay} dbias"
+            seen.append(op + lay)
         elif op == "conv1x1_bwd" and lay == "conv4":
             print("full-size check", op, lay, flush=True)
             x, dy = kw["x"], kw["dy"]
@@ -168,7 +203,7 @@ def test_c1_full_size_step_sampled(fused_tail):
     torch.cuda.synchronize()
     tail = ({"conv1x1_bn_maxpool_fwd", "conv1x1_bn_maxpool_bwd"} if fused_tail
             else {"conv1x1_fwdconv4", "bn_fwd_maxpool", "bn_bwd_maxpool", "conv1x1_bwdconv4"})
-    assert set(seen) == {"conv1x1_fwdconv0"} | tail
+    assert set(seen) == {"conv1x1_fwdconv0", "conv1x1_bn_bwdconv0", "conv1x1_bn_bwdconv2", "conv1x1_bn_bwdconv3"} | tail
     assert np.all(np.isfinite(arr.loss.cpu().numpy()))
     # Adam over the whole arena, in full, from the gradients the GPU just produced
     th0, g = f64(arr.theta), f64(arr.grad)

@@ -302,6 +302,87 @@ def test_conv1x1_bn_fwd(hb, dtype, B, Nb, Ci, Co, L, act, bias):
     check(host(Y2), host(Y), TOL[dtype], "Y (two-operator path)")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,Nb,Ci,Co,L,act,want_dx", [
+    (2, 3, 64, 64, 2500, 1, True),     # config 1's middle layers: ragged last slice, several slices per workgroup
+    (3, 2, 64, 128, 300, 2, True),     # 128 output channels (two dW tiles per wavefront)
+    (2, 2, 128, 128, 644, 1, True),    # both channel tiles 128 wide
+    (2, 2, 128, 64, 260, 0, True),     # 128 -> 64, no activation
+    (2, 4, 3, 64, 500, 1, False),      # a network's first layer: three input channels, no data gradient
+    (2, 2, 3, 64, 132, 1, True),       # ... with a data gradient (rows of W not 8-byte aligned: element loads)
+    (2, 2, 24, 40, 132, 1, True),      # channel counts below the tiles (zero padding inside the kernel)
+    (300, 2, 64, 64, 260, 1, True),    # many models: one workgroup per model walks all its slices
+    (2, 2, 64, 200, 128, 1, True),     # not the one-pass kernel's shape: the two operators, dz in the workspace
+])
+def test_conv1x1_bn_bwd(hb, dtype, B, Nb, Ci, Co, L, act, want_dx):
+    """BatchNorm backward + k=1 convolution backward in one call against the oracle's chain of the two
+    single operators with dz stored (rounded) in between.
+
+    The device forms dz in fp32 and rounds it to the storage type; the oracle forms it in float64.
+    The two roundings differ where the float64 value lies within the fp32 noise of dz of a bf16
+    rounding boundary -- between one element in 10^4 and a few in 10^3, each by one bf16 ulp
+    (2^-8..2^-7 of |dz|) -- so an element of dW, a sum of Nb * L products dz * x, can be off by a
+    few ulps of its largest terms: no tighter element-wise bound than the storage type's own holds
+    for it.  What the flips cannot do is move the error's root mean square: sqrt(5e-3) * 2^-8 ~ 3e-4
+    of rms(dW) at most.  So dW is held element-wise to the bf16 tolerance and in rms to 3e-4 (fp32
+    storage: 1e-5 element-wise); a dropped term, a wrong index or a misplaced tile is an error of
+    order one in either measure."""
+    print(f"conv1x1+bn bwd {dtype} B={B} Nb={Nb} {Ci}->{Co} L={L} act={act} dx={want_dx}", flush=True)
+    x = hi.normal(311, (Nb, B * Ci, L), dtype)
+    w = hi.normal(312, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    z = hi.snap(hi.normal(313, (Nb, B * Co, L)) * 2.0 + 1.5, dtype)
+    g = (hi.normal(314, (B * Co,)) * 0.5 + 1.0).astype(np.float32)
+    bt = hi.normal(315, (B * Co,)) * 0.3
+    dy = hi.normal(316, (Nb, B * Co, L), dtype)
+    xs, zs = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    # the oracle takes the activation mask from its own float64 pre-activation; an element whose
+    # pre-activation is within rounding of zero may legitimately take the other branch in fp32, so
+    # the few such elements of a large tensor are moved off the kink before either side sees them
+    for _ in range(4):
+        ry, rmean, rinv, _, _ = oa.bn_fwd(B, z, g, bt, 1e-5, 0.1, None, None)
+        knife = np.abs(ry) < 1e-5 * (np.abs(ry - bt[None, :, None]) + np.abs(bt)[None, :, None])
+        if act == 0 or knife.sum() == 0:
+            break
+        z = hi.snap(np.where(knife, z + 0.5, z), dtype)
+    assert act == 0 or knife.sum() == 0, "pre-activation on the kink"
+    X, W, Z, dY, G, Bt = dev(x, dtype), dev(w, dtype), dev(z, dtype), dev(dy, dtype), dev(g), dev(bt)
+    SM, SI = dev(rmean.astype(np.float32)), dev(rinv.astype(np.float32))
+    oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
+    dX = empty((Nb, B * Ci, L), dtype) if want_dx else None
+    dW, db = empty((B * Co, Ci), torch.float32), empty((B * Co,), torch.float32)
+    dG, dB = empty((B * Co,), torch.float32), empty((B * Co,), torch.float32)
+    nws = hb.conv1x1_bn_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype])
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    hb.conv1x1_bn_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Z, zs, dY, zs, G, Bt, SM, SI, dX, xs if want_dx else None,
+                      dW, db, dG, dB, act, 0.2, ws)
+    rmean32, rinv32 = rmean.astype(np.float32).astype(np.float64), rinv.astype(np.float32).astype(np.float64)
+    rdz, rdg, rdb = oa.bn_bwd(B, z, oops.act_bwd(ry, dy, oact, 0.2), g, rmean32, rinv32)
+    check(host(dG), rdg, f32_tol(dtype), "dgamma")
+    check(host(dB), rdb, f32_tol(dtype), "dbeta")
+    dzs = oops.store(rdz, dtype)
+    rdx, rdw, rdbias = oa.conv1x1_bwd(B, x, w, dzs)
+    if want_dx:
+        check(host(dX), rdx, TOL[dtype], "dX")
+    check(host(dW), rdw, 1e-5 if dtype == "f32" else TOL[dtype], "dW")
+    err = host(dW).astype(np.float64) - rdw
+    assert np.sqrt(np.mean(err * err)) <= (1e-5 if dtype == "f32" else 3e-4) * np.sqrt(np.mean(rdw * rdw)), "dW (rms)"
+    # dbias is a sum of terms that cancel (sum dz = 0 up to rounding): bound against the sum of magnitudes
+    assert np.abs(host(db) - rdbias).max() <= f32_tol(dtype) * np.abs(dzs).sum(axis=(0, 2)).max(), "dbias"
+    # bit-reproducible, and no output depends on what the workspace held before
+    ws.fill_(0xff)
+    dW2, db2 = empty((B * Co, Ci), torch.float32), empty((B * Co,), torch.float32)
+    dX2 = empty((Nb, B * Ci, L), dtype) if want_dx else None
+    hb.conv1x1_bn_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Z, zs, dY, zs, G, Bt, SM, SI, dX2, xs if want_dx else None,
+                      dW2, db2, dG, dB, act, 0.2, ws)
+    assert torch.equal(dW, dW2) and torch.equal(db, db2)
+    if want_dx:
+        assert torch.equal(dX, dX2)
+    with pytest.raises(RuntimeError):
+        hb.conv1x1_bn_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Z, zs, dY, zs, G, Bt, SM, SI, dX2, xs if want_dx else None,
+                          dW2, db2, dG, dB, act, 0.2, None)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("Nb", [32, 5, 64, 100])      # up to 64 samples: the column-in-registers kernels
 def test_bn_linear_layout_and_independence(hb, dtype, Nb):

@@ -95,7 +95,7 @@ def seg_probe(spec, seen):
         lay = kw.get("layer", "")
         if op in ("bn_fwd", "bn_bwd"):
             return base(op, layout="conv", **kw)
-        if op in ("conv1x1_fwd", "conv1x1_bwd", "maxpool_points"):
+        if op in ("conv1x1_fwd", "conv1x1_bwd", "conv1x1_bn_bwd", "maxpool_points"):
             return base(op, **kw)
         seen.append(op)
         if op == "linear_fwd":
@@ -191,7 +191,10 @@ def test_seg_every_call_in_place_and_chain(dtype):
 
     arr.forward_backward(probe)
     nconv, nh = len(spec.conv) - 1, len(spec.head) - 1
-    assert len(seen) == 2 * nconv + 1 + 1 + nh + (nh - 1) + 1 + (nh - 1) + nh + 2 + 1 + (nconv - 1) + 2 * nconv
+    # per-point layers whose BatchNorm backward + convolution backward run as one call: one probe instead of two
+    one_pass = sum(arr.one_pass)
+    assert seen.count("conv1x1_bn_bwd") == one_pass and (one_pass > 0) == (dtype == "bf16")
+    assert len(seen) == 2 * nconv + 1 + 1 + nh + (nh - 1) + 1 + (nh - 1) + nh + 2 + 1 + (nconv - 1) + 2 * nconv - one_pass
     states = [oseg.init_state(inp["params"][b]) for b in range(spec.B)]
     outs = oseg.array_train_step(spec, states, inp, 1)
     tol = CHAIN_TOL[dtype] if dtype == "bf16" else 1e-5 * (6 * nconv + 6 * nh + 8)

@@ -68,3 +68,14 @@ def check_tail_argmax(ya, ri, gi, absdot, Ci, scale, what=""):
     # an exact tie of the oracle's values at a lower index than the oracle's own cannot happen; at a higher one it
     # means the device skipped the first of two equal values only if they differ in its own arithmetic
     return int(mism.sum())
+
+
+def bn_preact_fp32(z, gamma, beta, mean, invstd):
+    """Pre-activation gamma * xhat + beta of a [N, C, L] tensor as the fp32 kernels form it -- xhat
+    rounded to fp32 after the subtraction and after the product, then one fused multiply-add whose
+    sign is the sign of the exact sum -- so that the branch an activation's derivative takes at
+    elements within rounding of zero is decided in the kernels' precision on both sides."""
+    f32 = np.float32
+    c = lambda a: np.asarray(a, np.float64).astype(f32)[None, :, None]
+    xh = (np.asarray(z, np.float64).astype(f32) - c(mean)) * c(invstd)
+    return c(gamma).astype(np.float64) * xh.astype(np.float64) + c(beta).astype(np.float64)
