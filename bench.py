@@ -40,7 +40,7 @@ class Tracer:
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
                      "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
                      "point_transform_fwd", "point_transform_bwd",
-                     "conv1x1_bn_maxpool_bwd", "conv1x1_bn_fwd")
+                     "conv1x1_bn_maxpool_bwd", "conv1x1_bn_fwd", "conv1x1_bn_bwd")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -93,6 +93,11 @@ def kernel_label(name, a):
         if dt == 1 and Ci % 8 == 0 and L % 4 == 0 and ((Ci <= 128 and Co >= 64) or (Ci <= 256 and Co >= 512)):
             return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_fwd_conv_part_kernel"
         return "conv1x1_bn_fwd: conv1x1 kernel + bn_fwd_conv_kernel"
+    if name == "conv1x1_bn_bwd":
+        B, Nb, Ci, Co, L, dt = a[:6]
+        if dt == 1 and Ci <= 128 and Co <= 128 and L % 4 == 0:
+            return "conv1x1_bn_bwd: bn_bwd_conv_coef_kernel + cbb_kernel + cbb_reduce_kernel"
+        return "conv1x1_bn_bwd: bn_bwd_conv_kernel + conv1x1 backward kernels"
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci <= 4 and L % 4 == 0:
@@ -223,6 +228,9 @@ def algorithmic_flops(name, a):
     if name in ("conv1x1_fwd", "conv1x1_bwd", "conv1x1_bn_fwd"):
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * Co * L
+    if name == "conv1x1_bn_bwd":       # weight gradient, and the data gradient if asked for (argument 17)
+        B, Nb, Ci, Co, L = a[:5]
+        return (4.0 if a[17] is not None else 2.0) * B * Nb * Ci * Co * L
     if name in ("attention_fwd", "attention_bwd"):      # 2 (forward) / 4 (backward) products of S x S x d per head
         B, N, S, E, H = a[:5]
         return (2 if name == "attention_fwd" else 4) * 2.0 * B * N * S * S * E
@@ -259,6 +267,10 @@ def algorithmic_bytes(name, a):
     if name == "conv1x1_bn_fwd":       # x and W in, z out; z in, y out
         B, Nb, Ci, Co, L, dt = a[:6]
         return (B * Nb * (Ci + 3 * Co) * L + B * Co * (Ci + 1)) * _es(dt)
+    if name == "conv1x1_bn_bwd":       # dY, z in (the batch means), then dY, z, x in and dX out; dz itself is not counted
+        B, Nb, Ci, Co, L, dt = a[:6]
+        has_dx = a[17] is not None
+        return (B * Nb * (4 * Co + (2 if has_dx else 1) * Ci) * L + B * Co * Ci) * _es(dt) + B * Co * (Ci + 3) * 4
     if name in ("linear_fwd", "linear_fwd_ws"):
         B, M, Fx, Fy, dt = a[:5]
         return B * (M * Fx + Fx * Fy + Fy + M * Fy) * _es(dt)

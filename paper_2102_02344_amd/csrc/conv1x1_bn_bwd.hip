@@ -16,15 +16,17 @@
 // data gradient and weight gradient as three kernels this leaves out one store and two loads of a
 // [Nb, B*Co, L] tensor and one load of dY and z.
 //
-// A workgroup (eight wavefronts, one per compute unit) is persistent: it walks over `tiles / G`
-// slices of one model, keeps that model's W^T tile and per-channel constants in LDS and its share of
-// dW in accumulator registers.  What keeps HBM busy is the number of bytes requested and not yet
-// returned (~100 KB per compute unit), far more than one slice: DEPTH slices are in flight in
-// registers, each set reissued as soon as its slice has been laid into LDS, and the loop over a round
-// of DEPTH slices has no exit in its middle, so that the wait on the oldest set leaves the younger ones
-// in flight.  At the end every workgroup writes fp32 partials of dW and dbias; a second kernel adds
-// the partials of a model in a fixed order.  Loads are raw buffer loads: anything outside an operand
-// is an out-of-range offset that returns zeros without a memory request.
+// A workgroup (eight wavefronts) is persistent: it walks over `tiles / G` slices of one model, keeps
+// that model's W^T tile and per-channel constants in LDS and its share of dW in accumulator
+// registers.  The next DEPTH slices are in flight in registers, each set reissued as soon as its
+// slice has been laid into LDS; a round of DEPTH slices has no exit in its middle (a slice past the
+// end runs empty), so that the wait on the oldest set leaves the younger ones in flight.  Measured:
+// one or two slices ahead are enough, three or four change nothing (the [Nb, C, L] layout makes every
+// slice 64..128 separate 256-byte row segments, and that access pattern, not the number of bytes in
+// flight, is what holds the kernel at about 4 TB/s), so DEPTH is set by the register budget.  At the
+// end every workgroup writes fp32 partials of dW and dbias; a second kernel adds the partials of a
+// model in a fixed order.  Loads are raw buffer loads: anything outside an operand is an
+// out-of-range offset that returns zeros without a memory request.
 #include "gemm_pf.h"
 #include "bn_common.h"
 
@@ -52,15 +54,16 @@ __device__ __forceinline__ float hi_f32(uint32_t v) { return __uint_as_float(v &
 
 constexpr int CBB_THREADS = 512;
 
-// CO, CI: channel tiles (64 or 128) that hold Co and Ci.  One workgroup of eight wavefronts per
-// compute unit; DEPTH slices are in flight in registers (what keeps HBM busy is the bytes requested
-// and not yet returned: ~100 KB per compute unit, far more than one slice).
-template <int CO, int CI>
+// CO, CI: channel tiles (64 or 128) that hold Co and Ci.
+template <int CO, int CI, bool HAS_DX>
 struct CbbCfg {
+  // Without a data gradient a 64 x 64 layer needs half the registers and LDS: two workgroups share a
+  // compute unit (one lays its slice into LDS while the other runs its matrix instructions).
+  static constexpr int WGS = (CO == 64 && CI == 64 && !HAS_DX) ? 2 : 1;
   static constexpr int SUBO = CO / 32;                 // 32-channel blocks of dY / z
   static constexpr int BPT = SUBO / 2;                 // 4 x 4 blocks of dY (and of z) per thread and slice
   static constexpr int XPT = CI / 16;                  // 8-byte pieces of x per thread and slice
-  static constexpr int DEPTH = (CO == 64 && CI == 64) ? 4 : ((CO == 128 && CI == 128) ? 1 : 2);   // register budget
+  static constexpr int DEPTH = WGS == 2 ? 1 : ((CO == 64 && CI == 64) ? 2 : ((CO == 128 && CI == 128) ? 1 : 2));   // register budget
   static constexpr int PT = CO * 2 + 16;               // row pitch of the k = co tiles (W^T, dz^T), bytes
   static constexpr int PN = 128 * 2 + 16;              // row pitch of the k = point tiles (dz, x)
   static constexpr int PS = 128 * 2 + 8;               // row pitch of the dX tile on its way out
@@ -75,12 +78,13 @@ struct CbbCfg {
   static constexpr int MMA_UNROLL = 2;                 // k-steps whose operand fragments are in registers at once (register budget)
   static_assert(DZT_BYTES + DZN_BYTES >= ST_BYTES, "staging tile must fit over the two dz tiles");
   static_assert(DZT_BYTES + DZN_BYTES >= 32 * CO * 4, "dbias scratch must fit over the two dz tiles");
-  static_assert(SMEM <= 160 * 1024, "LDS");
+  static_assert(SMEM * WGS <= 160 * 1024, "LDS");
 };
 
+// (The launch bound is the register budget: 2 * CBB_THREADS threads per compute unit where two workgroups share one.)
 template <int CO, int CI, bool HAS_DX>
-__global__ __launch_bounds__(CBB_THREADS, 1) void cbb_kernel(CbbArgs p) {
-  typedef CbbCfg<CO, CI> K;
+__global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void cbb_kernel(CbbArgs p) {
+  typedef CbbCfg<CO, CI, HAS_DX> K;
   constexpr int PT = K::PT, PN = K::PN, PS = K::PS, BPT = K::BPT, XPT = K::XPT, DEPTH = K::DEPTH;
   __shared__ __attribute__((aligned(16))) unsigned char smem[K::SMEM];
   unsigned char* Wts = smem;
@@ -361,13 +365,16 @@ __global__ __launch_bounds__(256) void cbb_reduce_kernel(const float* __restrict
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-int cbb_groups(int B, int Nb, int L) {
+int cbb_groups(int B, int Nb, int L, int per_cu) {
   const int tiles = Nb * ((L + 127) / 128);
-  int G = 256 / B;                          // one workgroup per compute unit
+  int G = 256 * per_cu / B;                 // workgroups the chip holds at once, per model
   if (G < 1) G = 1;
   if (G > tiles) G = tiles;
   return G;
 }
+
+// CbbCfg::WGS of the kernel the shape takes (the workspace is sized for the larger count: no data gradient)
+int cbb_per_cu(int Ci, int Co, bool has_dx) { return (Ci <= 64 && Co <= 64 && !has_dx) ? 2 : 1; }
 
 int cbb_point_halves(int Ci, int Co) { return (Ci <= 64 && Co <= 64) ? 2 : 1; }   // CbbCfg::KS of the kernel the shape takes
 
@@ -379,7 +386,7 @@ bool conv1x1_bn_bwd_streams(int B, int Ci, int Co, int L, int dtype) {
 }
 
 size_t conv1x1_bn_bwd_stream_bytes(int B, int Nb, int Ci, int Co, int L) {
-  const size_t slots = (size_t)cbb_groups(B, Nb, L) * cbb_point_halves(Ci, Co);
+  const size_t slots = (size_t)cbb_groups(B, Nb, L, cbb_per_cu(Ci, Co, false)) * cbb_point_halves(Ci, Co);
   return align256((size_t)B * Co * 8 * sizeof(float)) + slots * ((size_t)B * Co * Ci + (size_t)B * Co) * sizeof(float);
 }
 
@@ -409,7 +416,7 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
   a.x_g0 = xs[0]; a.x_g1 = xs[1]; a.x_ld = xs[2];
   a.dx_g0 = dX ? dxs[0] : 0; a.dx_g1 = dX ? dxs[1] : 0; a.dx_ld = dX ? dxs[2] : 0;
   a.B = B; a.Ci = Ci; a.Co = Co; a.L = L; a.Nb = Nb;
-  a.G = cbb_groups(B, Nb, L);
+  a.G = cbb_groups(B, Nb, L, cbb_per_cu(Ci, Co, dX != nullptr));
   a.slices = (L + 127) / 128;
   a.act = act; a.slope = slope;
   a.w_vec = (W && al(W, 8) && Ci % 4 == 0) ? 1 : 0;

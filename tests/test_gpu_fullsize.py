@@ -544,7 +544,10 @@ def test_c1_with_transform_subnetworks_full_size():
     """Config 1 with both transform sub-networks at the benchmarked size.  With the last Linear of
     each sub-network zero the matrices are identities, so loss and the main network's gradients must
     equal the plain config 1 array bit for bit (same kernels, same inputs; the transformed tensors
-    are exact copies); the sub-networks still receive finite, nonzero gradients."""
+    are exact copies); the sub-networks still receive finite, nonzero gradients.  One exception: the
+    first layer's backward also produces a data gradient here (for the input transform), which is
+    another instantiation of the kernel with another number of workgroups per model, so its weight and
+    bias gradients are the same sums in another fp32 order."""
     from paper_2102_02344_amd.arrays import FusedPointNetCls, FusedPointNetClsT
     ts = hi.PointNetTSpec(cls=hi.spec_c1())
     inp = hi.pointnet_t_inputs(ts)
@@ -563,6 +566,11 @@ def test_c1_with_transform_subnetworks_full_size():
     torch.cuda.synchronize()
     assert torch.equal(arr.loss, plain.loss) and bool(torch.isfinite(arr.loss).all())
     for name, _ in plain.shapes:
+        if name in ("conv0.w", "conv0.b"):
+            ga, gp = arr.g(name).double(), plain.g(name).double()
+            scale = plain.g("conv0.w").abs().max().item()
+            assert float((ga - gp).abs().max()) <= 1e-5 * scale, name
+            continue
         assert torch.equal(arr.g(name), plain.g(name)), name
     for k in hi.tnet_sizes(ts):
         g = arr.g(f"t{k}.fc{n}.w")
