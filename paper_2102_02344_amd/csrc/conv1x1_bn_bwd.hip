@@ -100,6 +100,8 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
   const int kq = t % 8, ng = (t / 8) % 32, sh = t / 256;   // 4 x 4 blocks: channel group of four, point group of four, 32-channel block parity
   const int b = blockIdx.x / p.G, w = blockIdx.x - b * p.G;
   const int tiles = p.Nb * p.slices;
+  // contiguous share of the model's slices: consecutive slices of one sample follow each other in time
+  const int share = (tiles + p.G - 1) / p.G, ubeg = w * share, uend = min(tiles, ubeg + share);
   constexpr bool has_dx = HAS_DX;
   // derivative of the activation where its argument is not positive (1 where it is): one select per element
   const float act_neg = p.act == HFTA_ACT_RELU ? 0.f : (p.act == HFTA_ACT_LEAKY ? p.slope : 1.f);
@@ -158,7 +160,7 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
   Regs q[DEPTH];
   const uint32_t dy_ldb = (uint32_t)(p.dy_ld * 2), z_ldb = (uint32_t)(p.z_ld * 2), x_ldb = (uint32_t)(p.x_ld * 2);
   auto issue = [&](Regs& g, int u) {
-    const bool live = u < tiles;
+    const bool live = u < uend;
     const int n = live ? u / p.slices : 0;
     const int l0 = live ? (u - n * p.slices) * 128 : 0;
     const __amdgpu_buffer_rsrc_t rd = pf_rsrc(p.dY + b * p.dy_g0 + n * p.dy_g1, p.dy_extent);
@@ -199,15 +201,15 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
     for (int j = 0; j < 4; ++j) bsum[i][j] = 0.f;
 
 #pragma unroll
-  for (int d = 0; d < DEPTH; ++d) issue(q[d], w + d * p.G);
-  for (int u0 = w; u0 < tiles; u0 += DEPTH * p.G) {
+  for (int d = 0; d < DEPTH; ++d) issue(q[d], ubeg + d);
+  for (int u0 = ubeg; u0 < uend; u0 += DEPTH) {
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
       // No way out of the loop from inside a round: a slice past the last one runs as an empty slice (its
       // loads request nothing, every point is "past the sample's end"), so the only back edge is taken with
       // all DEPTH slices reissued in order and the waits on the oldest one leave the younger ones in flight.
-      const int u = u0 + d * p.G;
-      const bool live = u < tiles;
+      const int u = u0 + d;
+      const bool live = u < uend;
       const int n = live ? u / p.slices : 0, l0 = live ? (u - n * p.slices) * 128 : p.slices * 128;
       const bool cok = l0 + ng * 4 + 4 <= p.L;
       // ---- dz of this slice, rounded, into both LDS tiles; x into its tile ----
@@ -252,7 +254,7 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
         *reinterpret_cast<uint2*>(xN + (id >> 5) * PN + (id & 31) * 8) = q[d].x[i];
       }
       __syncthreads();
-      issue(q[d], u + DEPTH * p.G);          // past the last slice: nothing is requested
+      issue(q[d], u + DEPTH);                // past the last slice: nothing is requested
 
       // ---- dW += dz x^T: (tile, point half) units of this wavefront ----
 #pragma unroll
