@@ -118,6 +118,43 @@ def test_validation_of_the_wider_entry_points(lib):
     assert tail_bwd(dt=0) == lib.EUNSUPPORTED
     assert tail_bwd(ws=None, nws=0) == lib.EWORKSPACE
 
+    # ---- conv + BatchNorm as one call per direction
+    assert raw.hfta_conv1x1_bn_fwd_workspace_bytes(8, 32, 64, 64, 2500, 1) == 8 * 32 * 20 * 64 * 2 * 4
+    assert raw.hfta_conv1x1_bn_fwd_workspace_bytes(8, 32, 64, 64, 2500, 0) == 0               # fp32: the two operators, no workspace
+    assert raw.hfta_conv1x1_bn_bwd_one_pass(8, 32, 64, 128, 2500, 1) == 1
+    assert raw.hfta_conv1x1_bn_bwd_one_pass(8, 32, 64, 128, 2500, 0) == 0                     # fp32
+    assert raw.hfta_conv1x1_bn_bwd_one_pass(8, 32, 128, 136, 2500, 1) == 0                    # Co > 128
+    assert raw.hfta_conv1x1_bn_bwd_one_pass(8, 32, 64, 64, 2502, 1) == 0                      # L % 4
+    assert raw.hfta_conv1x1_bn_bwd_one_pass(0, 32, 64, 64, 2500, 1) == 0
+    small = raw.hfta_conv1x1_bn_bwd_workspace_bytes(8, 32, 64, 64, 2500, 1)
+    assert 0 < small < 8 * 32 * 64 * 2500 * 2                  # constants and partials, not a dz-sized buffer
+    assert raw.hfta_conv1x1_bn_bwd_workspace_bytes(8, 32, 64, 64, 2500, 0) > 8 * 32 * 64 * 2500 * 4     # the two operators: dz + theirs
+    s64 = (C.c_int64 * 4)(64 * 2500, 8 * 64 * 2500, 2500, 1)
+    bad64 = (C.c_int64 * 4)(64 * 2500, 8 * 64 * 2500, 2500, 2)
+
+    def cb_fwd(B=8, X=one, xs=s64, rm=None, rv=None, act=1, eps=1e-5):
+        return raw.hfta_conv1x1_bn_fwd(B, 32, 64, 64, 2500, 1, X, xs, one, None, one, one, eps, 0.1, rm, rv, one, one,
+                                       one, s64, one, s64, act, 0.0, None, 0, None)
+    assert cb_fwd(X=None) == lib.EINVAL
+    assert cb_fwd(B=0) == lib.EINVAL
+    assert cb_fwd(rm=one) == lib.EINVAL                        # running statistics come as a pair
+    assert cb_fwd(eps=-1.0) == lib.EINVAL
+    assert cb_fwd(act=lib.ACT_TANH) == lib.EUNSUPPORTED
+    assert cb_fwd(xs=bad64) == lib.EUNSUPPORTED
+
+    def cb_bwd(B=8, Z=one, dX=one, W=one, dxs=s64, dW=one, act=1, ws=one, nws=1 << 40, dys=s64):
+        return raw.hfta_conv1x1_bn_bwd(B, 32, 64, 64, 2500, 1, one, s64, W, Z, s64, one, dys, one, one, one, one,
+                                       dX, dxs, dW, None, one, one, act, 0.0, ws, nws, None)
+    assert cb_bwd(Z=None) == lib.EINVAL
+    assert cb_bwd(B=0) == lib.EINVAL
+    assert cb_bwd(dW=None) == lib.EINVAL
+    assert cb_bwd(W=None) == lib.EINVAL                        # a data gradient needs the weights ...
+    assert cb_bwd(dxs=None) == lib.EINVAL                      # ... and its strides
+    assert cb_bwd(act=lib.ACT_GELU) == lib.EUNSUPPORTED
+    assert cb_bwd(dys=bad64) == lib.EUNSUPPORTED
+    assert cb_bwd(ws=None, nws=0) == lib.EWORKSPACE
+    assert cb_bwd(nws=small - 1) == lib.EWORKSPACE
+
     # ---- strided support operators of the segmentation head
     c3 = (C.c_int64 * 3)(16 * 64, 64, 1)
     assert raw.hfta_add_sample_bias(1, 2, 64, 0, 1, one, s4, one, c3, one, s4, None) == lib.EINVAL
