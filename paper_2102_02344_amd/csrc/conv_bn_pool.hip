@@ -85,7 +85,7 @@ __global__ __launch_bounds__(64) void cbp_coef_kernel(CbpArgs p) {
 }
 
 // ---- XX[b] = sum over (n, l) of x x^T, the Gram matrix of the layer input ------------------------
-// One workgroup accumulates the whole Ci x Ci matrix (Ci <= 128) over its share of 64-point tiles:
+// One workgroup accumulates the whole Ci x Ci matrix (Ci <= 128) over its share of 128-point tiles:
 // the tile is loaded ONCE (8-byte pieces, points contiguous = the contraction index), parked in one
 // of two LDS buffers, and serves as both operands of the matrix instruction; the next tile is in
 // flight in registers meanwhile.  Per-workgroup partial matrices are added in a fixed order by
@@ -97,22 +97,23 @@ struct GramArgs {
   uint32_t x_extent;
 };
 
-__global__ __launch_bounds__(GEMM_THREADS, 3) void gram_kernel(GramArgs p) {
-  constexpr int GP = 64 * 2 + 16;                        // bytes per LDS row: 64 points + pad
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gram_kernel(GramArgs p) {
+  constexpr int GPTS = 128;                              // points per tile: 256-byte row segments (64 points moved at 2.6 TB/s)
+  constexpr int GP = GPTS * 2 + 16;                      // bytes per LDS row: the tile's points + pad
   __shared__ __attribute__((aligned(16))) unsigned char smem[2][128 * GP];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int b = blockIdx.y, chunk = blockIdx.x;
   const int total = p.Nb * p.tiles_k;
   const int t0 = (int)((int64_t)total * chunk / p.chunks), t1 = (int)((int64_t)total * (chunk + 1) / p.chunks);
-  const int row = t >> 4, piece = t & 15;                // 16 rows x 16 pieces per pass, 8 passes
-  uint2 q[8];
+  const int row = t >> 5, piece = t & 31;                // 8 rows x 32 pieces per pass, 16 passes
+  uint2 q[16];
   auto load = [&](int tile) {
-    const int n = tile / p.tiles_k, l = (tile - n * p.tiles_k) * 64 + piece * 4;
+    const int n = tile / p.tiles_k, l = (tile - n * p.tiles_k) * GPTS + piece * 4;
     const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + b * p.xsb + n * p.xsn, p.x_extent);
 #pragma unroll
-    for (int h = 0; h < 8; ++h) {
-      const int ci = row + 16 * h;
+    for (int h = 0; h < 16; ++h) {
+      const int ci = row + 8 * h;
       const bool ok = tile < t1 && ci < p.Ci && l + 4 <= p.L;
       const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? (uint32_t)ci * (uint32_t)(p.xsc * 2) + (uint32_t)l * 2u : PF_OOB), 0, 0);
       q[h] = make_uint2(v.x, v.y);
@@ -130,11 +131,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 3) void gram_kernel(GramArgs p) {
   for (int tile = t0; tile < t1; ++tile) {
     unsigned char* buf = smem[(tile - t0) & 1];
 #pragma unroll
-    for (int h = 0; h < 8; ++h) *reinterpret_cast<uint2*>(buf + (row + 16 * h) * GP + piece * 8) = q[h];
+    for (int h = 0; h < 16; ++h) *reinterpret_cast<uint2*>(buf + (row + 8 * h) * GP + piece * 8) = q[h];
     __syncthreads();                                     // the other buffer was last read one step ago
     load(tile + 1);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
+    for (int s = 0; s < GPTS / 16; ++s) {
       bf16x8_t a[2], bb[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
@@ -180,7 +181,7 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const float* __restric
 }
 
 int gram_chunks(int B, int Nb, int L) {
-  const int total = Nb * ((L + 63) / 64);
+  const int total = Nb * ((L + 127) / 128);
   int c = (512 + B - 1) / B;
   if (c > total) c = total;
   return c < 1 ? 1 : c;
@@ -190,7 +191,7 @@ size_t gram_partial_bytes(int B, int Nb, int Ci, int L) { return (size_t)gram_ch
 // XX[b][ci][cj] for all models; `partial` holds gram_partial_bytes
 int gram_launch(int B, int Nb, int Ci, int L, const void* X, const int64_t xs[4], float* XX, float* partial,
                 uint32_t x_extent, hipStream_t st) {
-  GramArgs g{(const bf16_raw*)X, partial, XX, xs[0], xs[1], xs[2], Nb, Ci, L, (L + 63) / 64, gram_chunks(B, Nb, L), x_extent};
+  GramArgs g{(const bf16_raw*)X, partial, XX, xs[0], xs[1], xs[2], Nb, Ci, L, (L + 127) / 128, gram_chunks(B, Nb, L), x_extent};
   hipLaunchKernelGGL(gram_kernel, dim3((unsigned)g.chunks, (unsigned)B), dim3(GEMM_THREADS), 0, st, g);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   const int64_t count = (int64_t)B * Ci * Ci;
@@ -568,49 +569,40 @@ __global__ __launch_bounds__(1024) void cbp_sx_kernel(const float* part, float* 
 }
 
 // ---- dW[c][:] = gather term - a (dbeta E[x] + invstd dgamma Cov(z_c, x)), 8 channels per workgroup ----
-__global__ __launch_bounds__(128) void cbp_dw_kernel(CbpArgs p) {
+// One thread per (channel of the eight, input channel): the sums over ci and over the Nb argmax rows are
+// short dependent chains of loads, so the kernel is bound by their latency and wants threads, not work
+// per thread (128 threads walking the eight channels one after the other took 33 us on config 1).
+__global__ __launch_bounds__(1024) void cbp_dw_kernel(CbpArgs p) {
   constexpr int CB = 8;
   __shared__ float wrow[CB][128];
-  const int c0 = blockIdx.x * CB, b = blockIdx.y, cj = threadIdx.x;
-  for (int e = cj; e < CB * p.Ci; e += 128) {
-    const int cc = e / p.Ci, k = e - cc * p.Ci;
+  const int c0 = blockIdx.x * CB, b = blockIdx.y, cj = threadIdx.x & 127, e = threadIdx.x >> 7;
+  for (int i = threadIdx.x; i < CB * p.Ci; i += 1024) {
+    const int cc = i / p.Ci, k = i - cc * p.Ci;
     wrow[cc][k] = c0 + cc < p.Co ? bf16_to_f32(p.W[((int64_t)b * p.Co + c0 + cc) * p.Ci + k]) : 0.f;
   }
   __syncthreads();
-  if (cj >= p.Ci) return;
-  const float* XXb = p.XX + (int64_t)b * p.Ci * p.Ci;
-  float T[CB];
-#pragma unroll
-  for (int e = 0; e < CB; ++e) T[e] = 0.f;
+  const int c = c0 + e;
+  if (cj >= p.Ci || c >= p.Co) return;
+  float T = 0.f;
   if (p.Tin) {
-#pragma unroll
-    for (int e = 0; e < CB; ++e)
-      if (c0 + e < p.Co) T[e] = p.Tin[((int64_t)b * p.Co + c0 + e) * p.Ci + cj];
+    T = p.Tin[((int64_t)b * p.Co + c) * p.Ci + cj];
   } else {
+    const float* XXb = p.XX + (int64_t)b * p.Ci * p.Ci;
 #pragma unroll 8
-    for (int ci = 0; ci < p.Ci; ++ci) {                  // Ci is a multiple of 8 (host)
-      const float x = XXb[(int64_t)ci * p.Ci + cj];
-#pragma unroll
-      for (int e = 0; e < CB; ++e) T[e] = fmaf(wrow[e][ci], x, T[e]);
-    }
+    for (int ci = 0; ci < p.Ci; ++ci) T = fmaf(wrow[e][ci], XXb[(int64_t)ci * p.Ci + cj], T);   // Ci is a multiple of 8 (host)
   }
   const double m = (double)p.Nb * (double)p.L;
   const double sx = (double)p.SX[(int64_t)b * p.Ci + cj], ex = sx / m;
-#pragma unroll 1
-  for (int e = 0; e < CB; ++e) {
-    const int c = c0 + e;
-    if (c >= p.Co) break;
-    float sp = 0.f;
+  float sp = 0.f;
 #pragma unroll 8
-    for (int n = 0; n < p.Nb; ++n) {
-      const int64_t row = ((int64_t)b * p.Nb + n) * p.Co + c;
-      sp = fmaf(p.s[row], bf16_to_f32(p.xg[row * p.Ci + cj]), sp);
-    }
-    const CbpChan ch = p.chan[b * p.Co + c];
-    const double ezx = ((double)T[e] + (double)ch.bias * sx) / m;
-    const double dense = (double)ch.a * ((double)ch.dbeta * ex + (double)ch.invstd * (double)ch.dgamma * (ezx - (double)ch.mean * ex));
-    p.dW[((int64_t)b * p.Co + c) * p.Ci + cj] = (float)((double)sp - dense);
+  for (int n = 0; n < p.Nb; ++n) {
+    const int64_t row = ((int64_t)b * p.Nb + n) * p.Co + c;
+    sp = fmaf(p.s[row], bf16_to_f32(p.xg[row * p.Ci + cj]), sp);
   }
+  const CbpChan ch = p.chan[b * p.Co + c];
+  const double ezx = ((double)T + (double)ch.bias * sx) / m;
+  const double dense = (double)ch.a * ((double)ch.dbeta * ex + (double)ch.invstd * (double)ch.dgamma * (ezx - (double)ch.mean * ex));
+  p.dW[((int64_t)b * p.Co + c) * p.Ci + cj] = (float)((double)sp - dense);
 }
 
 size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -878,8 +870,8 @@ __global__ __launch_bounds__(128) void fbp_stats_kernel(FbpArgs p) {
 #pragma unroll
   for (int e = 0; e < CB; ++e) T[e] = 0.0;
   if (live) {
-#pragma unroll 8
-    for (int ci = 0; ci < p.Ci; ++ci) {                  // Ci is a multiple of 8 (host)
+#pragma unroll 16
+    for (int ci = 0; ci < p.Ci; ++ci) {                  // a chain of loads: sixteen in flight
       const double x = (double)XXb[(int64_t)ci * p.Ci + cj];
 #pragma unroll
       for (int e = 0; e < CB; ++e) T[e] = fma(wrow[e][ci], x, T[e]);
@@ -1075,7 +1067,7 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   if (!saved_moments)
     hipLaunchKernelGGL(cbp_sx_kernel, dim3((unsigned)((Ci + 15) / 16), (unsigned)B), dim3(1024), 0, st, a.SXpart, a.SX, Ci,
                        Nb * (int)grid.x);
-  hipLaunchKernelGGL(cbp_dw_kernel, dim3((unsigned)((Co + 7) / 8), (unsigned)B), dim3(128), 0, st, a);
+  hipLaunchKernelGGL(cbp_dw_kernel, dim3((unsigned)((Co + 7) / 8), (unsigned)B), dim3(1024), 0, st, a);
   return launch_status();
 }
 
