@@ -157,7 +157,8 @@ int hfta_conv1x1_fwd_sample_bias(int B, int Nb, int Ci, int Co, int L, int dtype
  * statistics.  With a workspace of hfta_conv1x1_bn_fwd_workspace_bytes (8-byte aligned) and a bf16
  * layer that the streaming convolution kernel takes, the convolution's epilogue leaves per-slice
  * sums there and Z is read once (for the normalisation) instead of twice; otherwise the two
- * operators run one after the other (no workspace needed). */
+ * operators run one after the other (no workspace needed).  Y == NULL: only Z and the statistics
+ * are produced (a consumer that normalises Z on load follows, see hfta_conv1x1_bn_prenorm_fwd). */
 size_t hfta_conv1x1_bn_fwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
 int hfta_conv1x1_bn_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                         const void* X, const int64_t xs[4], const void* W, const void* bias,
@@ -215,6 +216,42 @@ int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                         const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
                         void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
                         int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
+
+/* The same two calls for a chain of such blocks in which the activated tensor between two blocks is
+ * never stored (rows "Conv1d" and "BatchNorm1d"; the per-point layers of the point-cloud models):
+ * the input is given as the PREVIOUS block's stored pre-activation Xpre (strides xs) together with
+ * that block's BatchNorm constants in_gamma, in_beta, in_mean, in_invstd ([B][Ci] fp32, as
+ * hfta_bn_fwd left them) and its activation in_act in {NONE, RELU, LEAKY}; the kernels form
+ *   X = in_act(in_gamma (Xpre - in_mean) in_invstd + in_beta),  rounded to the storage dtype,
+ * on the way into LDS with the arithmetic of hfta_bn_fwd, i.e. the very values that block would
+ * have stored, and proceed as hfta_conv1x1_bn_fwd / hfta_conv1x1_bn_bwd on that X (in the backward
+ * call dX is the gradient with respect to X, what the previous block's backward takes as its dY).
+ * Results are bit-identical to storing X and calling the plain pair.  The previous block is run
+ * with Y == NULL.  Only the shapes both streaming kernels take: bf16, Ci % 8 == 0, Ci <= 128,
+ * 64 <= Co <= 128, L % 4 == 0 (hfta_conv1x1_bn_prenorm_supported returns 1), 8-byte aligned
+ * tensors with strides that are multiples of 4 elements; anything else is HFTA_EUNSUPPORTED with
+ * nothing launched (store the activated tensor and use the plain pair).  Workspaces:
+ * hfta_conv1x1_bn_fwd_workspace_bytes and hfta_conv1x1_bn_bwd_workspace_bytes, required here
+ * (HFTA_EWORKSPACE).  Y may be NULL in the forward call, dX in the backward call. */
+int hfta_conv1x1_bn_prenorm_supported(int B, int Nb, int Ci, int Co, int L, int dtype);
+int hfta_conv1x1_bn_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                                const void* Xpre, const int64_t xs[4],
+                                const float* in_gamma, const float* in_beta, const float* in_mean,
+                                const float* in_invstd, int in_act, float in_slope,
+                                const void* W, const void* bias, const float* gamma, const float* beta,
+                                float eps, float momentum, float* running_mean, float* running_var,
+                                float* save_mean, float* save_invstd, void* Z, const int64_t zs[4],
+                                void* Y, const int64_t ys[4], int act, float act_slope,
+                                void* workspace, size_t ws_bytes, void* stream);
+int hfta_conv1x1_bn_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                                const void* Xpre, const int64_t xs[4],
+                                const float* in_gamma, const float* in_beta, const float* in_mean,
+                                const float* in_invstd, int in_act, float in_slope,
+                                const void* W, const void* Z, const int64_t zs[4],
+                                const void* dY, const int64_t dys[4],
+                                const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
+                                void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
+                                int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * Fused Conv2d (row "Conv2d" -> grouped Conv2d with G = B; g = 1 per model).

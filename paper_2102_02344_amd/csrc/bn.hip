@@ -73,6 +73,7 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
       p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
     }
   }
+  if (!p.Y) return;                      // statistics only: a consumer normalises on load
   for (RowWalk w(chunks, NT); w.n < p.Nb;) {
     float v[BN_UNROLL][VEC];
     int n[BN_UNROLL], ch[BN_UNROLL];
@@ -130,6 +131,7 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_part_kernel(BnFwdArgs p, const
       p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
     }
   }
+  if (!p.Y) return;                      // statistics only: a consumer normalises on load
   for (RowWalk w(chunks, NT); w.n < p.Nb;) {
     float v[BN_UNROLL][VEC];
     int n[BN_UNROLL], ch[BN_UNROLL];
@@ -423,17 +425,38 @@ int bn_fwd_from_partials(int B, int Nb, int C, int L, int dtype, const void* X, 
                          const float* beta, float eps, float momentum, float* running_mean, float* running_var,
                          float* save_mean, float* save_invstd, void* Y, const int64_t ys[4], int act, float slope,
                          const float* part, int parts, const void* shift, hipStream_t st) {
-  if (dtype != HFTA_BF16 || B > 65535 || layout_kind(xs, L) != 1 || layout_kind(ys, L) != 1) return HFTA_EUNSUPPORTED;
+  // Y == nullptr: statistics only (mean, invstd, running statistics); nothing of size [Nb, C, L] is touched
+  if (dtype != HFTA_BF16 || B > 65535 || layout_kind(xs, L) != 1 || (Y && layout_kind(ys, L) != 1)) return HFTA_EUNSUPPORTED;
   BnFwdArgs a{X, Y, gamma, beta, running_mean, running_var, save_mean, save_invstd,
-              xs[0], xs[1], xs[2], ys[0], ys[1], ys[2], Nb, C, L, act, eps, momentum, slope};
+              xs[0], xs[1], xs[2], Y ? ys[0] : 0, Y ? ys[1] : 0, Y ? ys[2] : 0, Nb, C, L, act, eps, momentum, slope};
   const dim3 grid((unsigned)C, (unsigned)B);
-  const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
+  const bool v4 = vec_ok(X, xs, L, dtype) && (!Y || vec_ok(Y, ys, L, dtype));
   const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
   const bf16_raw* sv = (const bf16_raw*)shift;
   if (v4) { if (big) hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 4, 1024>), grid, dim3(1024), 0, st, a, part, parts, sv);
             else hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 4, 256>), grid, dim3(256), 0, st, a, part, parts, sv); }
   else { if (big) hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 1, 1024>), grid, dim3(1024), 0, st, a, part, parts, sv);
          else hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 1, 256>), grid, dim3(256), 0, st, a, part, parts, sv); }
+  return launch_status();
+}
+
+// Training statistics of a conv-layout tensor alone (mean, invstd, running statistics): the first pass of
+// the forward kernel, for a consumer that normalises on load.
+int bn_stats_conv(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
+                  const float* beta, float eps, float momentum, float* running_mean, float* running_var,
+                  float* save_mean, float* save_invstd, hipStream_t st) {
+  if (B > 65535 || layout_kind(xs, L) != 1) return HFTA_EUNSUPPORTED;
+  BnFwdArgs a{X, nullptr, gamma, beta, running_mean, running_var, save_mean, save_invstd,
+              xs[0], xs[1], xs[2], 0, 0, 0, Nb, C, L, HFTA_ACT_NONE, eps, momentum, 0.f};
+  const dim3 grid((unsigned)C, (unsigned)B);
+  const bool v4 = vec_ok(X, xs, L, dtype);
+  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
+#define HFTA_BN_STATS(T, V) \
+  do { if (big) hipLaunchKernelGGL((bn_fwd_conv_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a); \
+       else hipLaunchKernelGGL((bn_fwd_conv_kernel<T, V, 256>), grid, dim3(256), 0, st, a); } while (0)
+  if (dtype == HFTA_BF16) { if (v4) HFTA_BN_STATS(bf16_raw, 4); else HFTA_BN_STATS(bf16_raw, 1); }
+  else { if (v4) HFTA_BN_STATS(float, 4); else HFTA_BN_STATS(float, 1); }
+#undef HFTA_BN_STATS
   return launch_status();
 }
 

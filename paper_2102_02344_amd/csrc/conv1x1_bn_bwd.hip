@@ -47,6 +47,10 @@ struct CbbArgs {
   int B, Ci, Co, L, Nb, G, slices, act, w_vec;           // w_vec: rows of W can be read eight bytes at a time
   float slope;
   uint32_t dy_extent, z_extent, x_extent, w_extent;
+  // in_gamma != nullptr: X is the previous block's stored pre-activation; x = act_in(BatchNorm_in(X)), rounded to
+  // bf16, is formed on the way into LDS with the arithmetic of the BatchNorm kernels.  [B][Ci] each.
+  const float* in_gamma; const float* in_beta; const float* in_mean; const float* in_invstd;
+  int in_act; float in_slope;
 };
 
 __device__ __forceinline__ float lo_f32(uint32_t v) { return __uint_as_float(v << 16); }
@@ -70,7 +74,8 @@ struct CbbCfg {
   static constexpr int WT_BYTES = CI * PT, DZT_BYTES = 128 * PT, DZN_BYTES = CO * PN, XN_BYTES = CI * PN;
   static constexpr int ST_BYTES = CI * PS, CF_BYTES = CO * 32;
   static constexpr bool OVERLAY = (CO == 128 && CI == 128);   // the dX tile goes out over dz^T (LDS would not hold both)
-  static constexpr int SMEM = WT_BYTES + DZT_BYTES + DZN_BYTES + XN_BYTES + CF_BYTES + (OVERLAY ? 0 : ST_BYTES);
+  static constexpr int XC_BYTES = CI * 16;             // the input block's BatchNorm constants (with a data gradient: own region; without: over W^T)
+  static constexpr int SMEM = WT_BYTES + DZT_BYTES + DZN_BYTES + XN_BYTES + CF_BYTES + (OVERLAY ? 0 : ST_BYTES) + (HAS_DX ? XC_BYTES : 0);
   static constexpr int DXT = CI / 64;                  // 32 x 32 tiles of dX per wavefront (CI/32 x 4 tiles, 8 wavefronts)
   static constexpr int WTILES = (CO / 32) * (CI / 32); // 32 x 32 tiles of dW
   static constexpr int KS = WTILES == 4 ? 2 : 1;       // four tiles: the slice's points are split over two wavefronts per tile
@@ -94,6 +99,8 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
   unsigned char* cfb = xN + K::XN_BYTES;
   unsigned char* stg = K::OVERLAY ? dzT : cfb + K::CF_BYTES;
   const float4* cf = reinterpret_cast<const float4*>(cfb);
+  float4* xc = reinterpret_cast<float4*>(HAS_DX ? cfb + K::CF_BYTES + (K::OVERLAY ? 0 : K::ST_BYTES) : Wts);
+  static_assert(HAS_DX || K::WT_BYTES >= K::XC_BYTES, "constants fit over the unused W^T tile");
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int r = lane & 31, gsel = lane >> 5;
@@ -115,6 +122,12 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
     if (k < p.Co) c = *reinterpret_cast<const float4*>(p.coef + ((int64_t)b * p.Co + k) * 8 + (t & 1) * 4);
     reinterpret_cast<float4*>(cfb)[(t & 1) * CO + slot] = c;
   }
+  const bool xin = p.in_gamma != nullptr;
+  if (xin)
+    for (int k = t; k < CI; k += CBB_THREADS) {
+      const int64_t g = (int64_t)b * p.Ci + k;
+      xc[k] = k < p.Ci ? make_float4(p.in_mean[g], p.in_invstd[g], p.in_gamma[g], p.in_beta[g]) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
   if (has_dx && !p.w_vec) {
     // rows of W not 8-byte aligned (Ci % 4 != 0, e.g. three input channels): element by element, once per workgroup
     for (int i = t; i < K::WT_BYTES / 4; i += CBB_THREADS) reinterpret_cast<uint32_t*>(Wts)[i] = 0u;
@@ -251,7 +264,21 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
 #pragma unroll
       for (int i = 0; i < XPT; ++i) {
         const int id = t + CBB_THREADS * i;
-        *reinterpret_cast<uint2*>(xN + (id >> 5) * PN + (id & 31) * 8) = q[d].x[i];
+        uint2 xv = q[d].x[i];
+        if (xin) {
+          const float4 cn = xc[id >> 5];
+          const bool xok = l0 + (id & 31) * 4 + 4 <= p.L;
+          float v[4] = {lo_f32(xv.x), hi_f32(xv.x), lo_f32(xv.y), hi_f32(xv.y)};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float y = fmaf(cn.z, (v[e] - cn.x) * cn.y, cn.w);
+            float lo = p.in_act == HFTA_ACT_LEAKY ? p.in_slope * y : 0.f;      // what the activation returns where y <= 0
+            if (p.in_act == HFTA_ACT_NONE) lo = y;
+            v[e] = xok ? (y > 0.f ? y : lo) : 0.f;
+          }
+          xv = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        }
+        *reinterpret_cast<uint2*>(xN + (id >> 5) * PN + (id & 31) * 8) = xv;
       }
       __syncthreads();
       issue(q[d], u + DEPTH);                // past the last slice: nothing is requested
@@ -397,11 +424,15 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
                           const void* Z, const int64_t zs[4], const void* dY, const int64_t dys[4], const float* gamma,
                           const float* beta, const float* save_mean, const float* save_invstd, void* dX,
                           const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act, float slope,
-                          void* workspace, hipStream_t st) {
+                          void* workspace, hipStream_t st, const float* in_gamma, const float* in_beta,
+                          const float* in_mean, const float* in_invstd, int in_act, float in_slope) {
   auto al = [](const void* q, size_t a) { return (reinterpret_cast<uintptr_t>(q) % a) == 0; };
   auto s4 = [](const int64_t* s) { return s[0] % 4 == 0 && s[1] % 4 == 0 && s[2] % 4 == 0 && s[2] > 0 && s[3] == 1; };
   if (!al(X, 8) || !al(Z, 8) || !al(dY, 8) || !s4(xs) || !s4(zs) || !s4(dys) || !al(workspace, 16)) return HFTA_EUNSUPPORTED;
   if (dX && (!s4(dxs) || !al(dX, 8))) return HFTA_EUNSUPPORTED;
+  if (in_gamma && (!in_beta || !in_mean || !in_invstd ||
+                   (in_act != HFTA_ACT_NONE && in_act != HFTA_ACT_RELU && in_act != HFTA_ACT_LEAKY)))
+    return HFTA_EUNSUPPORTED;
   auto ext = [&](const int64_t* s, int C) { return ((int64_t)(C - 1) * s[2] + L) * 2; };
   const int64_t w_ext = (int64_t)Co * Ci * 2;
   if (ext(xs, Ci) >= (int64_t)1 << 31 || ext(zs, Co) >= (int64_t)1 << 31 || ext(dys, Co) >= (int64_t)1 << 31 || w_ext >= (int64_t)1 << 31)
@@ -421,6 +452,8 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
   a.G = cbb_groups(B, Nb, L, cbb_per_cu(Ci, Co, dX != nullptr));
   a.slices = (L + 127) / 128;
   a.act = act; a.slope = slope;
+  a.in_gamma = in_gamma; a.in_beta = in_beta; a.in_mean = in_mean; a.in_invstd = in_invstd;
+  a.in_act = in_act; a.in_slope = in_slope;
   a.w_vec = (W && al(W, 8) && Ci % 4 == 0) ? 1 : 0;
   a.dy_extent = (uint32_t)ext(dys, Co); a.z_extent = (uint32_t)ext(zs, Co); a.x_extent = (uint32_t)ext(xs, Ci);
   a.w_extent = (uint32_t)w_ext;

@@ -37,13 +37,18 @@ struct StreamArgs {
   // per (model, sample, 128-point slice) and channel the sums of (y - bias) and (y - bias)^2 over the
   // slice's points, [b * Nb + n][slice][Co][2]; the activation must be none.
   float* stat_part;
+  // Input given as the previous block's stored pre-activation (XF kernels): x = act_in(gamma (X - mean) invstd + beta),
+  // rounded to bf16, is formed on the way into LDS with the arithmetic of the BatchNorm kernels, so the
+  // product sees the bits that block would have stored.  [B][Ci] each.
+  const float* in_gamma; const float* in_beta; const float* in_mean; const float* in_invstd;
+  int in_act; float in_slope;
 };
 
 // ONE: the layer has a single 128-row W tile (Co <= 128), so the X tile is dead once the matrix
 // instructions have run and the output staging tile may lie over it: 37 KB of LDS instead of 52 KB
 // at KT = 64, i.e. four workgroups per compute unit instead of three (register budget via launch
 // bounds).
-template <int KT, bool ONE = false>
+template <int KT, bool ONE = false, bool XF = false>
 __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kernel(StreamArgs p) {
   constexpr int PITCH = KT * 2 + 16;                   // bytes per LDS row: KT bf16 + pad
   constexpr int TILE = 128 * PITCH;
@@ -51,7 +56,7 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
   constexpr int SREG = TILE > STAGE ? TILE : STAGE;    // W tile, then the output staging tile
   constexpr int SUB = KT / 32;
   constexpr int SMEM = ONE ? (2 * TILE > STAGE ? 2 * TILE : STAGE) : TILE + SREG;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM + (XF ? KT * 16 : 0)];
   unsigned char* Xs = ONE ? smem + TILE : smem;        // ONE: [W tile | X tile], staging over both
   unsigned char* Ws = ONE ? smem : smem + TILE;
 
@@ -73,6 +78,14 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
   const __amdgpu_buffer_rsrc_t rw = pf_rsrc(p.W + (int64_t)b * p.Co * p.Ci, p.w_extent);
   const __amdgpu_buffer_rsrc_t rx = pf_rsrc(p.X + b * p.x_g0 + n * p.x_g1, p.x_extent);
 
+  if (XF) {                              // the input block's BatchNorm constants, one float4 per input channel
+    float4* ic = reinterpret_cast<float4*>(smem + SMEM);
+    for (int k = t; k < KT; k += GEMM_THREADS) {
+      const int64_t g = (int64_t)b * p.Ci + k;
+      ic[k] = k < p.Ci ? make_float4(p.in_mean[g], p.in_invstd[g], p.in_gamma[g], p.in_beta[g]) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __syncthreads();
+  }
   // ---- X tile: 4(ci) x 4(points) blocks, transposed in registers on the way into LDS ----
   {
     const int kq = t % 8, ng = t / 8;
@@ -88,6 +101,26 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
         const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? (uint32_t)k * ldb + (uint32_t)c * 2u : PF_OOB), 0, 0);
         q[s][j] = make_uint2(v.x, v.y);
       }
+    if (XF) {
+      const float4* ic = reinterpret_cast<const float4*>(smem + SMEM);
+      const bool cok = c + 4 <= p.L;       // points past the sample's end stay zero (the statistics epilogue counts on it)
+#pragma unroll
+      for (int s = 0; s < SUB; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float4 cn = ic[s * 32 + 4 * kq + j];
+          float v[4] = {__uint_as_float(q[s][j].x << 16), __uint_as_float(q[s][j].x & 0xffff0000u),
+                        __uint_as_float(q[s][j].y << 16), __uint_as_float(q[s][j].y & 0xffff0000u)};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float y = fmaf(cn.z, (v[e] - cn.x) * cn.y, cn.w);
+            float lo = p.in_act == HFTA_ACT_LEAKY ? p.in_slope * y : 0.f;      // what the activation returns where y <= 0
+            if (p.in_act == HFTA_ACT_NONE) lo = y;
+            v[e] = cok ? (y > 0.f ? y : lo) : 0.f;
+          }
+          q[s][j] = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        }
+    }
 #pragma unroll
     for (int s = 0; s < SUB; ++s) {
       const uint32_t a0 = q[s][0].x, a1 = q[s][1].x, a2 = q[s][2].x, a3 = q[s][3].x;
@@ -188,13 +221,19 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
 }
 
 // Returns HFTA_OK when launched, HFTA_EUNSUPPORTED when the problem is not this kernel's.
+// in_gamma != nullptr: X is the previous block's stored pre-activation, normalised and activated on load
+// (Ci <= 128 only).
 int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
                        const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st,
-                       float* stat_part) {
+                       float* stat_part, const float* in_gamma, const float* in_beta, const float* in_mean,
+                       const float* in_invstd, int in_act, float in_slope) {
   auto al = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; };
   if (Ci > 256 || Ci % 8 != 0 || Co < 64 || L % 4 != 0) return HFTA_EUNSUPPORTED;
   if (Ci > 128 && Co < STREAM_WIDE_MIN_CO) return HFTA_EUNSUPPORTED;
   if (act == HFTA_ACT_TANH || act == HFTA_ACT_GELU || (stat_part && act != HFTA_ACT_NONE)) return HFTA_EUNSUPPORTED;
+  if (in_gamma && (Ci > 128 || !in_beta || !in_mean || !in_invstd ||
+                   (in_act != HFTA_ACT_NONE && in_act != HFTA_ACT_RELU && in_act != HFTA_ACT_LEAKY)))
+    return HFTA_EUNSUPPORTED;
   if (!al(W, 16) || !al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0) return HFTA_EUNSUPPORTED;
   const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2, w_ext = (int64_t)Co * Ci * 2;
   if (x_ext >= (int64_t)1 << 31 || w_ext >= (int64_t)1 << 31) return HFTA_EUNSUPPORTED;
@@ -212,7 +251,15 @@ int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, cons
   }
   a.w_extent = (uint32_t)w_ext; a.x_extent = (uint32_t)x_ext;
   a.stat_part = stat_part;
+  a.in_gamma = in_gamma; a.in_beta = in_beta; a.in_mean = in_mean; a.in_invstd = in_invstd;
+  a.in_act = in_act; a.in_slope = in_slope;
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
+  if (in_gamma) {
+    if (Ci <= 64 && Co <= 128) hipLaunchKernelGGL((conv1x1_stream_kernel<64, true, true>), grid, dim3(GEMM_THREADS), 0, st, a);
+    else if (Ci <= 64) hipLaunchKernelGGL((conv1x1_stream_kernel<64, false, true>), grid, dim3(GEMM_THREADS), 0, st, a);
+    else hipLaunchKernelGGL((conv1x1_stream_kernel<128, false, true>), grid, dim3(GEMM_THREADS), 0, st, a);
+    return launch_status();
+  }
   if (Ci <= 64 && Co <= 128) hipLaunchKernelGGL((conv1x1_stream_kernel<64, true>), grid, dim3(GEMM_THREADS), 0, st, a);
   else if (Ci <= 64) hipLaunchKernelGGL(conv1x1_stream_kernel<64>, grid, dim3(GEMM_THREADS), 0, st, a);
   else if (Ci <= 128) hipLaunchKernelGGL(conv1x1_stream_kernel<128>, grid, dim3(GEMM_THREADS), 0, st, a);

@@ -7,7 +7,8 @@
 namespace hfta {
 int conv1x1_stream_fwd(int B, int Nb, int Ci, int Co, int L, const void* X, const int64_t xs[4], const void* W,
                        const void* bias, void* Y, const int64_t ys[4], int act, float slope, hipStream_t st,
-                       float* stat_part = nullptr);
+                       float* stat_part = nullptr, const float* in_gamma = nullptr, const float* in_beta = nullptr,
+                       const float* in_mean = nullptr, const float* in_invstd = nullptr, int in_act = 0, float in_slope = 0.f);
 // BatchNorm forward whose statistics come from per-slice partial sums (bn.hip)
 int bn_fwd_from_partials(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
                          const float* beta, float eps, float momentum, float* running_mean, float* running_var,
@@ -19,7 +20,11 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
                           const void* Z, const int64_t zs[4], const void* dY, const int64_t dys[4], const float* gamma,
                           const float* beta, const float* save_mean, const float* save_invstd, void* dX,
                           const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act, float slope,
-                          void* workspace, hipStream_t st);
+                          void* workspace, hipStream_t st, const float* in_gamma = nullptr, const float* in_beta = nullptr,
+                          const float* in_mean = nullptr, const float* in_invstd = nullptr, int in_act = 0, float in_slope = 0.f);
+int bn_stats_conv(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
+                  const float* beta, float eps, float momentum, float* running_mean, float* running_var,
+                  float* save_mean, float* save_invstd, hipStream_t st);
 }
 
 using namespace hfta;
@@ -471,11 +476,12 @@ int hfta_conv1x1_bn_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const v
                         float act_slope, void* workspace, size_t ws_bytes, void* stream) {
   int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
   if (rc != HFTA_OK) return rc;
-  if (!X || !W || !Z || !Y || !xs || !zs || !ys || !gamma || !beta || !save_mean || !save_invstd || !(eps >= 0.f))
+  // Y == NULL: statistics only (the activated output is not formed; a consumer normalises Z on load)
+  if (!X || !W || !Z || !xs || !zs || (Y && !ys) || !gamma || !beta || !save_mean || !save_invstd || !(eps >= 0.f))
     return HFTA_EINVAL;
   if ((running_mean == nullptr) != (running_var == nullptr)) return HFTA_EINVAL;
   if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
-  if (xs[3] != 1 || zs[3] != 1 || ys[3] != 1) return HFTA_EUNSUPPORTED;
+  if (xs[3] != 1 || zs[3] != 1 || (Y && ys[3] != 1)) return HFTA_EUNSUPPORTED;
   hipStream_t st = as_stream(stream);
   const size_t need = hfta_conv1x1_bn_fwd_workspace_bytes(B, Nb, Ci, Co, L, dtype);
   if (dtype == HFTA_BF16 && need && workspace && ws_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 8 == 0) {
@@ -488,8 +494,50 @@ int hfta_conv1x1_bn_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const v
   }
   rc = hfta_conv1x1_fwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, HFTA_ACT_NONE, 0.f, stream);
   if (rc != HFTA_OK) return rc;
+  if (!Y)
+    return hfta::bn_stats_conv(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
+                               save_invstd, st);
   return hfta_bn_fwd(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
                      save_invstd, Y, ys, act, act_slope, stream);
+}
+
+// ---- the same pair of calls with the input given as the previous block's stored pre-activation ----
+int hfta_conv1x1_bn_prenorm_supported(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  return check_conv1x1(B, Nb, Ci, Co, L, dtype) == HFTA_OK && dtype == HFTA_BF16 && Ci % 8 == 0 && Ci <= 128 && Co >= 64 &&
+                 Co <= 128 && L % 4 == 0 && hfta::conv1x1_bn_bwd_streams(B, Ci, Co, L, dtype)
+             ? 1 : 0;
+}
+
+static bool in_norm_ok(const float* g, const float* b, const float* m, const float* i, int act) {
+  return g && b && m && i && (act == HFTA_ACT_NONE || act == HFTA_ACT_RELU || act == HFTA_ACT_LEAKY);
+}
+
+int hfta_conv1x1_bn_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* Xpre, const int64_t xs[4],
+                                const float* in_gamma, const float* in_beta, const float* in_mean, const float* in_invstd,
+                                int in_act, float in_slope, const void* W, const void* bias, const float* gamma,
+                                const float* beta, float eps, float momentum, float* running_mean, float* running_var,
+                                float* save_mean, float* save_invstd, void* Z, const int64_t zs[4], void* Y,
+                                const int64_t ys[4], int act, float act_slope, void* workspace, size_t ws_bytes,
+                                void* stream) {
+  int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
+  if (rc != HFTA_OK) return rc;
+  if (!Xpre || !W || !Z || !xs || !zs || (Y && !ys) || !gamma || !beta || !save_mean || !save_invstd || !(eps >= 0.f))
+    return HFTA_EINVAL;
+  if (!in_gamma || !in_beta || !in_mean || !in_invstd) return HFTA_EINVAL;
+  if ((running_mean == nullptr) != (running_var == nullptr)) return HFTA_EINVAL;
+  if (!in_norm_ok(in_gamma, in_beta, in_mean, in_invstd, in_act)) return HFTA_EUNSUPPORTED;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (xs[3] != 1 || zs[3] != 1 || (Y && ys[3] != 1)) return HFTA_EUNSUPPORTED;
+  if (!hfta_conv1x1_bn_prenorm_supported(B, Nb, Ci, Co, L, dtype)) return HFTA_EUNSUPPORTED;
+  const size_t need = hfta_conv1x1_bn_fwd_workspace_bytes(B, Nb, Ci, Co, L, dtype);
+  if (!workspace || ws_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 8 != 0) return HFTA_EWORKSPACE;
+  hipStream_t st = as_stream(stream);
+  float* part = reinterpret_cast<float*>(workspace);
+  rc = hfta::conv1x1_stream_fwd(B, Nb, Ci, Co, L, Xpre, xs, W, bias, Z, zs, HFTA_ACT_NONE, 0.f, st, part, in_gamma, in_beta,
+                                in_mean, in_invstd, in_act, in_slope);
+  if (rc != HFTA_OK) return rc;
+  return hfta::bn_fwd_from_partials(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var,
+                                    save_mean, save_invstd, Y, ys, act, act_slope, part, Nb * ((L + 127) / 128), bias, st);
 }
 
 // The data gradient of a narrow layer (Co <= 128, or Co <= 256 under at least 512 inputs) is a k=1 convolution of dY with the transposed
@@ -612,6 +660,30 @@ int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const v
   if (rc != HFTA_OK) return rc;
   unsigned char* rest = reinterpret_cast<unsigned char*>(workspace) + dzb;
   return hfta_conv1x1_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, workspace, ds, dX, dxs, dW, nullptr, rest, ws_bytes - dzb, stream);
+}
+
+
+int hfta_conv1x1_bn_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* Xpre, const int64_t xs[4],
+                                const float* in_gamma, const float* in_beta, const float* in_mean, const float* in_invstd,
+                                int in_act, float in_slope, const void* W, const void* Z, const int64_t zs[4],
+                                const void* dY, const int64_t dys[4], const float* gamma, const float* beta,
+                                const float* save_mean, const float* save_invstd, void* dX, const int64_t dxs[4],
+                                float* dW, float* dbias, float* dgamma, float* dbeta, int act, float act_slope,
+                                void* workspace, size_t ws_bytes, void* stream) {
+  int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
+  if (rc != HFTA_OK) return rc;
+  if (!Xpre || !xs || !Z || !zs || !dY || !dys || !gamma || !beta || !save_mean || !save_invstd || !dW || !dgamma || !dbeta)
+    return HFTA_EINVAL;
+  if (!in_gamma || !in_beta || !in_mean || !in_invstd) return HFTA_EINVAL;
+  if (dX && (!W || !dxs)) return HFTA_EINVAL;
+  if (!in_norm_ok(in_gamma, in_beta, in_mean, in_invstd, in_act)) return HFTA_EUNSUPPORTED;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (xs[3] != 1 || zs[3] != 1 || dys[3] != 1 || (dX && dxs[3] != 1)) return HFTA_EUNSUPPORTED;
+  if (!hfta_conv1x1_bn_prenorm_supported(B, Nb, Ci, Co, L, dtype)) return HFTA_EUNSUPPORTED;
+  if (!workspace || ws_bytes < hfta::conv1x1_bn_bwd_stream_bytes(B, Nb, Ci, Co, L)) return HFTA_EWORKSPACE;
+  return hfta::conv1x1_bn_bwd_stream(B, Nb, Ci, Co, L, Xpre, xs, W, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd, dX,
+                                     dxs, dW, dbias, dgamma, dbeta, act, act_slope, workspace, as_stream(stream), in_gamma,
+                                     in_beta, in_mean, in_invstd, in_act, in_slope);
 }
 
 }  // extern "C"

@@ -383,6 +383,77 @@ def test_conv1x1_bn_bwd(hb, dtype, B, Nb, Ci, Co, L, act, want_dx):
                           dW2, db2, dG, dB, act, 0.2, None)
 
 
+@pytest.mark.parametrize("B,Nb,Ci,Co,L,in_act,act,want_y", [
+    (2, 3, 64, 64, 2500, 1, 1, False),   # config 1's middle layers: ragged last slice, activated output not formed
+    (3, 2, 64, 128, 300, 1, 1, True),    # 64 -> 128 with the activated output stored (what feeds the one-operator tail)
+    (2, 2, 128, 128, 644, 2, 0, False),  # 128-deep reduction, LeakyReLU on the input block, none on this one
+    (2, 2, 24, 72, 132, 0, 2, True),     # channel counts below the tiles, no activation on the input block
+])
+def test_conv1x1_bn_prenorm(hb, B, Nb, Ci, Co, L, in_act, act, want_y):
+    """A chain of conv -> BatchNorm -> act blocks in which the activated tensor between two blocks is never
+    stored: the second block takes the first one's stored pre-activation and BatchNorm constants and forms
+    its input on load.  Forward and backward must equal, bit for bit, the plain pair of calls on the stored
+    activated tensor (same arithmetic, same kernels), and the forward is checked against the oracle's chain."""
+    dtype = "bf16"
+    print(f"conv1x1+bn prenorm B={B} Nb={Nb} {Ci}->{Co} L={L} in_act={in_act} act={act} y={want_y}", flush=True)
+    assert hb.conv1x1_bn_prenorm_supported(B, Nb, Ci, Co, L, DT[dtype])
+    xpre = hi.snap(hi.normal(321, (Nb, B * Ci, L)) * 1.5 + 0.4, dtype)
+    gi = (hi.normal(322, (B * Ci,)) * 0.5 + 1.0).astype(np.float32)
+    bi = (hi.normal(323, (B * Ci,)) * 0.3).astype(np.float32)
+    w = hi.normal(324, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    b = hi.normal(325, (B * Co,), dtype)
+    g = (hi.normal(326, (B * Co,)) * 0.5 + 1.0).astype(np.float32)
+    bt = (hi.normal(327, (B * Co,)) * 0.3).astype(np.float32)
+    dy = hi.normal(328, (Nb, B * Co, L), dtype)
+    xs, zs = conv_strides(B, Ci, L), conv_strides(B, Co, L)
+    Xp, Gi, Bi, W, Bs, G, Bt, dY = dev(xpre, dtype), dev(gi), dev(bi), dev(w, dtype), dev(b, dtype), dev(g), dev(bt), dev(dy, dtype)
+    f32 = torch.float32
+    # the input block's BatchNorm on the device: its statistics, and (for the plain pair) its stored output
+    MI, II, X = empty((B * Ci,), f32), empty((B * Ci,), f32), empty((Nb, B * Ci, L), dtype)
+    hb.bn_fwd(B, Nb, Ci, L, DT[dtype], Xp, xs, Gi, Bi, 1e-5, 0.1, None, None, MI, II, X, xs, in_act, 0.2)
+    nws = max(hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype]), hb.conv1x1_bn_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype]))
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    out = {}
+    for kind in ("plain", "prenorm"):
+        Z, Y = empty((Nb, B * Co, L), dtype), (empty((Nb, B * Co, L), dtype) if want_y else None)
+        SM, SI = empty((B * Co,), f32), empty((B * Co,), f32)
+        RM, RV = dev(np.zeros(B * Co, np.float32)), dev(np.ones(B * Co, np.float32))
+        dX, dW, db = empty((Nb, B * Ci, L), dtype), empty((B * Co, Ci), f32), empty((B * Co,), f32)
+        dG, dB = empty((B * Co,), f32), empty((B * Co,), f32)
+        ws.fill_(0x5a)
+        if kind == "plain":
+            hb.conv1x1_bn_fwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Bs, G, Bt, 1e-5, 0.1, RM, RV, SM, SI, Z, zs, Y,
+                              zs if want_y else None, act, 0.2, ws)
+            hb.conv1x1_bn_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Z, zs, dY, zs, G, Bt, SM, SI, dX, xs, dW, db, dG, dB, act, 0.2, ws)
+        else:
+            hb.conv1x1_bn_prenorm_fwd(B, Nb, Ci, Co, L, DT[dtype], Xp, xs, Gi, Bi, MI, II, in_act, 0.2, W, Bs, G, Bt, 1e-5, 0.1,
+                                      RM, RV, SM, SI, Z, zs, Y, zs if want_y else None, act, 0.2, ws)
+            hb.conv1x1_bn_prenorm_bwd(B, Nb, Ci, Co, L, DT[dtype], Xp, xs, Gi, Bi, MI, II, in_act, 0.2, W, Z, zs, dY, zs, G, Bt,
+                                      SM, SI, dX, xs, dW, db, dG, dB, act, 0.2, ws)
+        out[kind] = dict(Z=Z, Y=Y, SM=SM, SI=SI, RM=RM, RV=RV, dX=dX, dW=dW, db=db, dG=dG, dB=dB)
+    for k, v in out["plain"].items():
+        if v is not None:
+            assert torch.equal(v, out["prenorm"][k]), f"{k} differs from the plain pair on the stored activated tensor"
+    # against the oracle: its own chain with the activated tensor stored (rounded) in between
+    oin = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[in_act]
+    ry_in = oa.bn_fwd(B, xpre, gi, bi, 1e-5, 0.1, None, None)[0]
+    xo = oops.store(oops.act_fwd(ry_in, oin, 0.2), dtype)
+    check(host(X), xo, TOL[dtype], "input block's activated tensor")
+    rz = oa.conv1x1_fwd(B, host(X).astype(np.float64), w, b)      # on the bits the device formed on load (equal to X, shown above)
+    check(host(out["prenorm"]["Z"]), rz, TOL[dtype], "Z")
+    zdev = host(out["prenorm"]["Z"]).astype(np.float64)
+    ry, rmean, rinv, _, _ = oa.bn_fwd(B, zdev, g, bt, 1e-5, 0.1, None, None)
+    check(host(out["prenorm"]["SM"]), rmean, 1e-5, "mean")
+    check(host(out["prenorm"]["SI"]), rinv, 1e-5, "invstd")
+    if want_y:
+        oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
+        check(host(out["prenorm"]["Y"]), oops.act_fwd(ry, oact, 0.2), TOL[dtype], "Y")
+    # an input the kernels do not take comes back as a status code with nothing launched
+    with pytest.raises(RuntimeError):
+        hb.conv1x1_bn_prenorm_fwd(B, Nb, Ci, Co, L, DT["f32"], Xp, xs, Gi, Bi, MI, II, in_act, 0.2, W, Bs, G, Bt, 1e-5, 0.1,
+                                  None, None, SM, SI, Z, zs, None, None, act, 0.2, ws)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("Nb", [32, 5, 64, 100])      # up to 64 samples: the column-in-registers kernels
 def test_bn_linear_layout_and_independence(hb, dtype, Nb):
