@@ -40,7 +40,8 @@ class Tracer:
                      "add_sample_bias", "sum_points", "add_strided", "softmax_xent_points",
                      "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
                      "point_transform_fwd", "point_transform_bwd",
-                     "conv1x1_bn_maxpool_bwd", "conv1x1_bn_fwd", "conv1x1_bn_bwd")
+                     "conv1x1_bn_maxpool_bwd", "conv1x1_bn_fwd", "conv1x1_bn_bwd", "conv1x1_bn_prenorm_fwd",
+                     "conv1x1_bn_prenorm_bwd")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -93,6 +94,10 @@ def kernel_label(name, a):
         if dt == 1 and Ci % 8 == 0 and L % 4 == 0 and ((Ci <= 128 and Co >= 64) or (Ci <= 256 and Co >= 512)):
             return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_fwd_conv_part_kernel"
         return "conv1x1_bn_fwd: conv1x1 kernel + bn_fwd_conv_kernel"
+    if name == "conv1x1_bn_prenorm_fwd":     # the same kernels as the plain call, the input normalised on load
+        return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_fwd_conv_part_kernel"
+    if name == "conv1x1_bn_prenorm_bwd":
+        return "conv1x1_bn_bwd: bn_bwd_conv_coef_kernel + cbb_kernel + cbb_reduce_kernel"
     if name == "conv1x1_bn_bwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci <= 128 and Co <= 128 and L % 4 == 0:
@@ -228,9 +233,13 @@ def algorithmic_flops(name, a):
     if name in ("conv1x1_fwd", "conv1x1_bwd", "conv1x1_bn_fwd"):
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * Co * L
-    if name == "conv1x1_bn_bwd":       # weight gradient, and the data gradient if asked for (argument 17)
+    if name in ("conv1x1_bn_bwd", "conv1x1_bn_prenorm_bwd"):       # weight gradient, and the data gradient if asked for
         B, Nb, Ci, Co, L = a[:5]
-        return (4.0 if a[17] is not None else 2.0) * B * Nb * Ci * Co * L
+        dx = a[17] if name == "conv1x1_bn_bwd" else a[23]
+        return (4.0 if dx is not None else 2.0) * B * Nb * Ci * Co * L
+    if name == "conv1x1_bn_prenorm_fwd":
+        B, Nb, Ci, Co, L = a[:5]
+        return 2.0 * B * Nb * Ci * Co * L
     if name in ("attention_fwd", "attention_bwd"):      # 2 (forward) / 4 (backward) products of S x S x d per head
         B, N, S, E, H = a[:5]
         return (2 if name == "attention_fwd" else 4) * 2.0 * B * N * S * S * E
@@ -264,12 +273,13 @@ def algorithmic_bytes(name, a):
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         return (B * Nb * (Ci + Co) * L + B * Co * (Ci + 1)) * _es(dt)
-    if name == "conv1x1_bn_fwd":       # x and W in, z out; z in, y out
+    if name in ("conv1x1_bn_fwd", "conv1x1_bn_prenorm_fwd"):       # x and W in, z out; z in, y out (if y is asked for)
         B, Nb, Ci, Co, L, dt = a[:6]
-        return (B * Nb * (Ci + 3 * Co) * L + B * Co * (Ci + 1)) * _es(dt)
-    if name == "conv1x1_bn_bwd":       # dY, z in (the batch means), then dY, z, x in and dX out; dz itself is not counted
+        y = a[20] if name == "conv1x1_bn_fwd" else a[26]
+        return (B * Nb * (Ci + (3 if y is not None else 1) * Co) * L + B * Co * (Ci + 1)) * _es(dt)
+    if name in ("conv1x1_bn_bwd", "conv1x1_bn_prenorm_bwd"):   # dY, z in (the batch means), then dY, z, x in and dX out; dz itself is not counted
         B, Nb, Ci, Co, L, dt = a[:6]
-        has_dx = a[17] is not None
+        has_dx = (a[17] if name == "conv1x1_bn_bwd" else a[23]) is not None
         return (B * Nb * (4 * Co + (2 if has_dx else 1) * Ci) * L + B * Co * Ci) * _es(dt) + B * Co * (Ci + 3) * 4
     if name in ("linear_fwd", "linear_fwd_ws"):
         B, M, Fx, Fy, dt = a[:5]

@@ -213,7 +213,16 @@ class FusedPointNetCls(ParamArena):
             self.fused_tail = hb.conv1x1_bn_maxpool_fwd_workspace_bytes(*geo) > 0
         nz = self.nconv - 1 if self.fused_tail else self.nconv
         self.z = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:1 + nz]]
-        self.a = [torch.empty(Nb, B * c, L, **act) for c in spec.conv[1:-1]]   # the last one is never stored
+        # prenorm[i]: layer i takes layer i-1's stored pre-activation and normalises it on load (forward and
+        # backward), so the activated tensor a[i-1] between the two is never stored.  The layer in front of the
+        # tail keeps its activated output (the tail operator reads it).
+        self.prenorm = [False] * self.nconv
+        if not self.unfused:
+            for i in range(1, self.nconv - 1):
+                self.prenorm[i] = hb.conv1x1_bn_prenorm_supported(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt)
+        self.a = [None if (i + 1 < self.nconv - 1 and self.prenorm[i + 1]) else torch.empty(Nb, B * c, L, **act)
+                  for i, c in enumerate(spec.conv[1:-1])]                        # the last layer's is never stored
+        self._atmp = None
         cmax = max(spec.conv[1:1 + nz])
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
         Cp = spec.conv[-1]
@@ -254,6 +263,24 @@ class FusedPointNetCls(ParamArena):
             self.drop_mask = torch.from_numpy(inp["drop_mask"]).to(self.dev)
 
     # ------------------------------------------------------------------ one step
+    def _act(self, i):
+        """Activated output of per-point layer i: the stored tensor, or -- for a layer whose consumer normalises
+        on load, and only for tests that look at every tensor -- the same values written out by the BatchNorm
+        kernel from the stored pre-activation (statistics into scratch, running statistics untouched)."""
+        if self.a[i] is not None:
+            return self.a[i]
+        s, B, Nb, L = self.spec, self.B, self.Nb, self.L
+        co, k, cs = s.conv[i + 1], f"conv{i}", _cs(self.B, s.conv[i + 1], self.L)
+        if self._atmp is None:
+            cmax = max(s.conv[1:-1])
+            self._atmp = (torch.empty(Nb * B * cmax * L, dtype=self.tdt, device=self.dev),
+                          torch.empty(B * cmax, dtype=torch.float32, device=self.dev),
+                          torch.empty(B * cmax, dtype=torch.float32, device=self.dev))
+        t = self._atmp[0][:Nb * B * co * L].view(Nb, B * co, L)
+        hb.bn_fwd(B, Nb, co, L, self.dt, self.z[i], cs, self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.BN_EPS,
+                  self.BN_MOMENTUM, None, None, self._atmp[1], self._atmp[2], t, cs, hb.ACT_RELU)
+        return t
+
     def forward_backward(self, probe=None):
         """One forward + backward pass.  ``probe(op, **tensors)``, if given, is called after
         every library call with the tensors that call read and wrote (tests use it to check
@@ -284,16 +311,28 @@ class FusedPointNetCls(ParamArena):
                 continue
             if i < self.nconv - 1:
                 # convolution + BatchNorm + ReLU in one call: the convolution's epilogue leaves the
-                # statistics' partial sums, so z is read once for the normalisation
-                hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
-                                  self.master(k + ".bn.g"), self.master(k + ".bn.b"), eps, mom,
-                                  self.running[k + ".bn.rm"], self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"],
-                                  self.saved[k + ".bn.invstd"], self.z[i], _cs(B, co, L), self.a[i], _cs(B, co, L),
-                                  hb.ACT_RELU, 0.0, self.ws)
-                P("conv1x1_fwd", layer=k, x=x, w=self.w(k + ".w"), b=self.w(k + ".b"), y=self.z[i])
-                P("bn_fwd", layer=k, layout="conv", x=self.z[i], g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"),
-                  y=self.a[i], mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"])
-                x, ci = self.a[i], co
+                # statistics' partial sums, so z is read once for the normalisation -- or not at all here,
+                # where the next layer normalises it on load (y is None)
+                y = self.a[i]
+                bnp = (self.master(k + ".bn.g"), self.master(k + ".bn.b"), eps, mom, self.running[k + ".bn.rm"],
+                       self.running[k + ".bn.rv"], self.saved[k + ".bn.mean"], self.saved[k + ".bn.invstd"])
+                if self.prenorm[i]:
+                    kp = f"conv{i - 1}"
+                    hb.conv1x1_bn_prenorm_fwd(B, Nb, ci, co, L, dt, self.z[i - 1], _cs(B, ci, L), self.master(kp + ".bn.g"),
+                                              self.master(kp + ".bn.b"), self.saved[kp + ".bn.mean"],
+                                              self.saved[kp + ".bn.invstd"], hb.ACT_RELU, 0.0, self.w(k + ".w"),
+                                              self.w(k + ".b"), *bnp, self.z[i], _cs(B, co, L), y,
+                                              None if y is None else _cs(B, co, L), hb.ACT_RELU, 0.0, self.ws)
+                else:
+                    hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"), *bnp,
+                                      self.z[i], _cs(B, co, L), y, None if y is None else _cs(B, co, L), hb.ACT_RELU, 0.0,
+                                      self.ws)
+                if probe is not None:
+                    P("conv1x1_fwd", layer=k, x=self._act(i - 1) if self.prenorm[i] else x, w=self.w(k + ".w"),
+                      b=self.w(k + ".b"), y=self.z[i])
+                    P("bn_fwd", layer=k, layout="conv", x=self.z[i], g=self.master(k + ".bn.g"), b=self.master(k + ".bn.b"),
+                      y=self._act(i), mean=self.saved[k + ".bn.mean"], invstd=self.saved[k + ".bn.invstd"])
+                x, ci = y, co
                 continue
             hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), self.w(k + ".w"), self.w(k + ".b"),
                            self.z[i], _cs(B, co, L))
@@ -421,11 +460,21 @@ class FusedPointNetCls(ParamArena):
                 if i in self.unfused:
                     self._layer_bwd_unfused(i, xin, ci, co, da, dxin)
                 else:
-                    hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), self.z[i], cs, da, cs,
-                                      self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],
-                                      self.saved[k + ".bn.invstd"], dxin, None if i == 0 else _cs(B, ci, L),
-                                      self.g(k + ".w"), self.g(k + ".b"), self.g(k + ".bn.g"), self.g(k + ".bn.b"),
-                                      hb.ACT_RELU, 0.0, self.ws)
+                    bnp = (self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],
+                           self.saved[k + ".bn.invstd"])
+                    out = (dxin, None if i == 0 else _cs(B, ci, L), self.g(k + ".w"), self.g(k + ".b"), self.g(k + ".bn.g"),
+                           self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.ws)
+                    if self.prenorm[i]:
+                        kp = f"conv{i - 1}"
+                        hb.conv1x1_bn_prenorm_bwd(B, Nb, ci, co, L, dt, self.z[i - 1], _cs(B, ci, L), self.master(kp + ".bn.g"),
+                                                  self.master(kp + ".bn.b"), self.saved[kp + ".bn.mean"],
+                                                  self.saved[kp + ".bn.invstd"], hb.ACT_RELU, 0.0, self.w(k + ".w"),
+                                                  self.z[i], cs, da, cs, *bnp, *out)
+                        if probe is not None:
+                            xin = self._act(i - 1)
+                    else:
+                        hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, _cs(B, ci, L), self.w(k + ".w"), self.z[i], cs, da, cs,
+                                          *bnp, *out)
                     P("conv1x1_bn_bwd", layer=k, x=xin, w=self.w(k + ".w"), z=self.z[i], dy=da.view(Nb, B * co, L),
                       g=self.master(k + ".bn.g"), bt=self.master(k + ".bn.b"), mean=self.saved[k + ".bn.mean"],
                       invstd=self.saved[k + ".bn.invstd"], dx=None if i == 0 else dxin.view(Nb, B * ci, L),
