@@ -155,6 +155,34 @@ def test_validation_of_the_wider_entry_points(lib):
     assert cb_bwd(ws=None, nws=0) == lib.EWORKSPACE
     assert cb_bwd(nws=small - 1) == lib.EWORKSPACE
 
+    # ---- ... and with the input given as the previous block's stored pre-activation
+    assert raw.hfta_conv1x1_bn_prenorm_supported(8, 32, 64, 128, 2500, 1) == 1
+    assert raw.hfta_conv1x1_bn_prenorm_supported(8, 32, 64, 128, 2500, 0) == 0                # fp32
+    assert raw.hfta_conv1x1_bn_prenorm_supported(8, 32, 3, 64, 2500, 1) == 0                  # Ci % 8
+    assert raw.hfta_conv1x1_bn_prenorm_supported(8, 32, 128, 1024, 2500, 1) == 0              # Co > 128
+    assert raw.hfta_conv1x1_bn_prenorm_supported(8, 32, 64, 32, 2500, 1) == 0                 # Co < 64
+    assert raw.hfta_conv1x1_bn_fwd(8, 32, 64, 64, 2500, 0, one, s64, one, None, one, one, 1e-5, 0.1, None, None, one, one,
+                                   one, s64, one, None, 1, 0.0, None, 0, None) == lib.EINVAL   # an output without strides
+
+    def pn_fwd(dt=1, Ci=64, ig=one, in_act=1, ws=one, nws=1 << 40, Y=None, ys=None):
+        return raw.hfta_conv1x1_bn_prenorm_fwd(8, 32, Ci, 64, 2500, dt, one, s64, ig, one, one, one, in_act, 0.0, one, None,
+                                               one, one, 1e-5, 0.1, None, None, one, one, one, s64, Y, ys, 1, 0.0, ws, nws, None)
+    assert pn_fwd(ig=None) == lib.EINVAL
+    assert pn_fwd(Y=one, ys=None) == lib.EINVAL
+    assert pn_fwd(dt=0) == lib.EUNSUPPORTED
+    assert pn_fwd(Ci=60) == lib.EUNSUPPORTED
+    assert pn_fwd(in_act=lib.ACT_TANH) == lib.EUNSUPPORTED
+    assert pn_fwd(ws=None, nws=0) == lib.EWORKSPACE
+
+    def pn_bwd(dt=1, ig=one, dW=one, W=one, ws=one, nws=1 << 40):
+        return raw.hfta_conv1x1_bn_prenorm_bwd(8, 32, 64, 64, 2500, dt, one, s64, ig, one, one, one, 1, 0.0, W, one, s64, one,
+                                               s64, one, one, one, one, one, s64, dW, None, one, one, 1, 0.0, ws, nws, None)
+    assert pn_bwd(ig=None) == lib.EINVAL
+    assert pn_bwd(dW=None) == lib.EINVAL
+    assert pn_bwd(W=None) == lib.EINVAL
+    assert pn_bwd(dt=0) == lib.EUNSUPPORTED
+    assert pn_bwd(nws=small - 1) == lib.EWORKSPACE
+
     # ---- strided support operators of the segmentation head
     c3 = (C.c_int64 * 3)(16 * 64, 64, 1)
     assert raw.hfta_add_sample_bias(1, 2, 64, 0, 1, one, s4, one, c3, one, s4, None) == lib.EINVAL
