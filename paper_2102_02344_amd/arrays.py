@@ -1301,7 +1301,13 @@ class _PointChain:
         nz = self.nconv - 1 if self.fused_tail else self.nconv
         self.z = [torch.empty(Nb, B * c, L, **act) for c in self.conv[1:1 + nz]]
         na = self.nconv if not self.head else self.nconv - 1            # a chain without a head keeps its last activation
-        self.a = [torch.empty(Nb, B * c, L, **act) for c in self.conv[1:1 + na]]
+        # prenorm[i]: layer i normalises layer i-1's stored pre-activation on load, a[i-1] is never stored
+        # (the layer in front of the tail keeps its output: the tail operator reads it)
+        self.prenorm = [False] * self.nconv
+        for i in range(1, na):
+            self.prenorm[i] = hb.conv1x1_bn_prenorm_supported(B, Nb, self.conv[i], self.conv[i + 1], L, dt)
+        self.a = [None if (i + 1 < na and self.prenorm[i + 1]) else torch.empty(Nb, B * c, L, **act)
+                  for i, c in enumerate(self.conv[1:1 + na])]
         cmax = max(self.conv)
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
         self.one_pass = [_bn_bwd_one_pass(B, Nb, self.conv[i], self.conv[i + 1], L, dt) for i in range(self.nconv)]
@@ -1346,9 +1352,18 @@ class _PointChain:
                                           hb.ACT_RELU, 0.0, ws)
                 break
             if not tail:
-                hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), A.w(k + ".w"), A.w(k + ".b"), *self._bn(k),
-                                  self.z[i], _cs(B, co, L), self.a[i], _cs(B, co, L), hb.ACT_RELU, 0.0, ws)
-                x, ci = self.a[i], co
+                y = self.a[i]
+                ys = None if y is None else _cs(B, co, L)
+                if self.prenorm[i]:
+                    kp = f"{self.px}conv{self.cb + i - 1}"
+                    hb.conv1x1_bn_prenorm_fwd(B, Nb, ci, co, L, dt, self.z[i - 1], _cs(B, ci, L), A.master(kp + ".bn.g"),
+                                              A.master(kp + ".bn.b"), A.saved[kp + ".bn.mean"], A.saved[kp + ".bn.invstd"],
+                                              hb.ACT_RELU, 0.0, A.w(k + ".w"), A.w(k + ".b"), *self._bn(k), self.z[i],
+                                              _cs(B, co, L), y, ys, hb.ACT_RELU, 0.0, ws)
+                else:
+                    hb.conv1x1_bn_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), A.w(k + ".w"), A.w(k + ".b"), *self._bn(k),
+                                      self.z[i], _cs(B, co, L), y, ys, hb.ACT_RELU, 0.0, ws)
+                x, ci = y, co
                 continue
             hb.conv1x1_fwd(B, Nb, ci, co, L, dt, x, _cs(B, ci, L), A.w(k + ".w"), A.w(k + ".b"), self.z[i], _cs(B, co, L))
             hb.bn_fwd_maxpool(B, Nb, co, L, dt, self.z[i], _cs(B, co, L), *self._bn(k), self.pooled, self.pool_idx,
@@ -1427,9 +1442,15 @@ class _PointChain:
             if not tail and self.one_pass[i]:
                 # BatchNorm backward + convolution backward in one call; its dX must not share da's buffer
                 dxin = self.dbuf[cur][:Nb * B * ci * L] if need_dx else None
-                hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, xs, A.w(k + ".w"), self.z[i], cs, da, cs, *bn, dxin,
-                                  xs if need_dx else None, A.g(k + ".w"), A.g(k + ".b"), A.g(k + ".bn.g"), A.g(k + ".bn.b"),
-                                  hb.ACT_RELU, 0.0, ws)
+                out = (dxin, xs if need_dx else None, A.g(k + ".w"), A.g(k + ".b"), A.g(k + ".bn.g"), A.g(k + ".bn.b"),
+                       hb.ACT_RELU, 0.0, ws)
+                if self.prenorm[i]:
+                    kp = f"{self.px}conv{self.cb + i - 1}"
+                    hb.conv1x1_bn_prenorm_bwd(B, Nb, ci, co, L, dt, self.z[i - 1], xs, A.master(kp + ".bn.g"),
+                                              A.master(kp + ".bn.b"), A.saved[kp + ".bn.mean"], A.saved[kp + ".bn.invstd"],
+                                              hb.ACT_RELU, 0.0, A.w(k + ".w"), self.z[i], cs, da, cs, *bn, *out)
+                else:
+                    hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, xs, A.w(k + ".w"), self.z[i], cs, da, cs, *bn, *out)
                 da, cur = dxin, cur ^ 1
                 continue
             dz = self.dbuf[cur][:Nb * B * co * L]
