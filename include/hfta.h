@@ -437,6 +437,36 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                                 float* dgamma, float* dbeta, int act, float act_slope,
                                 void* workspace, size_t ws_bytes, void* stream);
 
+/* The same operator at the end of a chain of conv -> BatchNorm -> act blocks whose activated tensors
+ * are not stored: X is given as the previous block's stored pre-activation Xpre with that block's
+ * BatchNorm constants (in_gamma, in_beta, in_mean, in_invstd: [B][Ci] fp32; in_act in {NONE, RELU,
+ * LEAKY}), and every kernel of the operator that reads X forms
+ *   X = in_act(in_gamma (Xpre - in_mean) in_invstd + in_beta),  rounded to the storage dtype,
+ * on load with the arithmetic of hfta_bn_fwd (see hfta_conv1x1_bn_prenorm_fwd).  Results are
+ * bit-identical to storing X and calling the plain pair.  Shapes, workspaces, other arguments and
+ * errors as the plain pair; the backward call takes the convolution output at the argmax (zhit),
+ * not Z; dX is the gradient with respect to X. */
+int hfta_conv1x1_bn_maxpool_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                                        const void* Xpre, const int64_t xs[4],
+                                        const float* in_gamma, const float* in_beta, const float* in_mean,
+                                        const float* in_invstd, int in_act, float in_slope,
+                                        const void* W, const void* bias, const float* gamma, const float* beta,
+                                        float eps, float momentum, float* running_mean, float* running_var,
+                                        float* save_mean, float* save_invstd,
+                                        void* V, int32_t* idx, const int64_t vs[3], float* zhit, float* saved_moments,
+                                        int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
+int hfta_conv1x1_bn_maxpool_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
+                                        const void* Xpre, const int64_t xs[4],
+                                        const float* in_gamma, const float* in_beta, const float* in_mean,
+                                        const float* in_invstd, int in_act, float in_slope,
+                                        const void* W, const void* bias, const float* zhit, const float* saved_moments,
+                                        const void* dV, const int32_t* idx, const int64_t vs[3],
+                                        const float* gamma, const float* beta,
+                                        const float* save_mean, const float* save_invstd,
+                                        void* dX, const int64_t dxs[4], float* dW, float* dbias,
+                                        float* dgamma, float* dbeta, int act, float act_slope,
+                                        void* workspace, size_t ws_bytes, void* stream);
+
 
 /* ------------------------------------------------------------------------
  * Fused Adam over the parameter arena of all B models (section "Our Proposal:

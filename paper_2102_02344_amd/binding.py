@@ -76,6 +76,8 @@ _SIGS = {
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
     "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 21 + [_i, _f, _p, _sz, _p]),
+    "hfta_conv1x1_bn_maxpool_prenorm_fwd": (_i, [_i] * 6 + [_p] * 6 + [_i, _f] + [_p] * 4 + [_f, _f] + [_p] * 9 + [_i, _f, _p, _sz, _p]),
+    "hfta_conv1x1_bn_maxpool_prenorm_bwd": (_i, [_i] * 6 + [_p] * 6 + [_i, _f] + [_p] * 17 + [_i, _f, _p, _sz, _p]),
     "hfta_point_transform_fwd": (_i, [_i] * 6 + [_p] * 6),
     "hfta_point_transform_bwd": (_i, [_i] * 6 + [_p] * 9),
     "hfta_softmax_xent_rows_workspace_bytes": (_sz, [_i, _i]),
@@ -360,6 +362,31 @@ def conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, zhit,
                                             _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dX), _strides(dxs),
                                             _ptr(dW), _ptr(dbias), _ptr(dgamma), _ptr(dbeta), act, act_slope, wp, wb,
                                             _stream(stream)), "hfta_conv1x1_bn_maxpool_bwd")
+
+
+def conv1x1_bn_maxpool_prenorm_fwd(B, Nb, Ci, Co, L, dtype, Xpre, xs, in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope, W,
+                                   bias, gamma, beta, eps, momentum, running_mean, running_var, save_mean, save_invstd, V, idx,
+                                   vs, zhit, saved_moments, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_conv1x1_bn_maxpool_prenorm_fwd(B, Nb, Ci, Co, L, dtype, _ptr(Xpre), _strides(xs), _ptr(in_gamma),
+                                                    _ptr(in_beta), _ptr(in_mean), _ptr(in_invstd), in_act, in_slope, _ptr(W),
+                                                    _ptr(bias), _ptr(gamma), _ptr(beta), eps, momentum, _ptr(running_mean),
+                                                    _ptr(running_var), _ptr(save_mean), _ptr(save_invstd), _ptr(V), _ptr(idx),
+                                                    _strides(vs, 3), _ptr(zhit), _ptr(saved_moments), act, act_slope, wp, wb,
+                                                    _stream(stream)), "hfta_conv1x1_bn_maxpool_prenorm_fwd")
+
+
+def conv1x1_bn_maxpool_prenorm_bwd(B, Nb, Ci, Co, L, dtype, Xpre, xs, in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope, W,
+                                   bias, zhit, saved_moments, dV, idx, vs, gamma, beta, save_mean, save_invstd, dX, dxs, dW,
+                                   dbias, dgamma, dbeta, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(_lib.hfta_conv1x1_bn_maxpool_prenorm_bwd(B, Nb, Ci, Co, L, dtype, _ptr(Xpre), _strides(xs), _ptr(in_gamma),
+                                                    _ptr(in_beta), _ptr(in_mean), _ptr(in_invstd), in_act, in_slope, _ptr(W),
+                                                    _ptr(bias), _ptr(zhit), _ptr(saved_moments), _ptr(dV), _ptr(idx),
+                                                    _strides(vs, 3), _ptr(gamma), _ptr(beta), _ptr(save_mean),
+                                                    _ptr(save_invstd), _ptr(dX), _strides(dxs), _ptr(dW), _ptr(dbias),
+                                                    _ptr(dgamma), _ptr(dbeta), act, act_slope, wp, wb, _stream(stream)),
+           "hfta_conv1x1_bn_maxpool_prenorm_bwd")
 
 
 def conv1x1_bn_maxpool_saved_floats(B, Ci, Co):

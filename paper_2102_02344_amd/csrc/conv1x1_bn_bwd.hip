@@ -29,6 +29,7 @@
 // out-of-range offset that returns zeros without a memory request.
 #include "gemm_pf.h"
 #include "bn_common.h"
+#include "in_norm.h"
 
 namespace hfta {
 
@@ -266,17 +267,7 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
         const int id = t + CBB_THREADS * i;
         uint2 xv = q[d].x[i];
         if (xin) {
-          const float4 cn = xc[id >> 5];
-          const bool xok = l0 + (id & 31) * 4 + 4 <= p.L;
-          float v[4] = {lo_f32(xv.x), hi_f32(xv.x), lo_f32(xv.y), hi_f32(xv.y)};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float y = fmaf(cn.z, (v[e] - cn.x) * cn.y, cn.w);
-            float lo = p.in_act == HFTA_ACT_LEAKY ? p.in_slope * y : 0.f;      // what the activation returns where y <= 0
-            if (p.in_act == HFTA_ACT_NONE) lo = y;
-            v[e] = xok ? (y > 0.f ? y : lo) : 0.f;
-          }
-          xv = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          xv = in_norm_apply4(xv, xc[id >> 5], l0 + (id & 31) * 4 + 4 <= p.L, p.in_act, p.in_slope);
         }
         *reinterpret_cast<uint2*>(xN + (id >> 5) * PN + (id & 31) * 8) = xv;
       }

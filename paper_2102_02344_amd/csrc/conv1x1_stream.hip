@@ -12,6 +12,7 @@
 // points >= L, the W tile after the last) is an out-of-range offset that returns zeros without a
 // memory request, so the loop has no branches around its loads.
 #include "gemm_pf.h"
+#include "in_norm.h"
 
 namespace hfta {
 
@@ -107,19 +108,7 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
 #pragma unroll
       for (int s = 0; s < SUB; ++s)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float4 cn = ic[s * 32 + 4 * kq + j];
-          float v[4] = {__uint_as_float(q[s][j].x << 16), __uint_as_float(q[s][j].x & 0xffff0000u),
-                        __uint_as_float(q[s][j].y << 16), __uint_as_float(q[s][j].y & 0xffff0000u)};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float y = fmaf(cn.z, (v[e] - cn.x) * cn.y, cn.w);
-            float lo = p.in_act == HFTA_ACT_LEAKY ? p.in_slope * y : 0.f;      // what the activation returns where y <= 0
-            if (p.in_act == HFTA_ACT_NONE) lo = y;
-            v[e] = cok ? (y > 0.f ? y : lo) : 0.f;
-          }
-          q[s][j] = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-        }
+        for (int j = 0; j < 4; ++j) q[s][j] = in_norm_apply4(q[s][j], ic[s * 32 + 4 * kq + j], cok, p.in_act, p.in_slope);
     }
 #pragma unroll
     for (int s = 0; s < SUB; ++s) {

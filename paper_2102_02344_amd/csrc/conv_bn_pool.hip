@@ -17,6 +17,7 @@
 // the 1.3 GB tensor of the headline workload is neither read nor written.
 #include "gemm_pf.h"
 #include "bn_common.h"
+#include "in_norm.h"
 
 using namespace hfta;
 
@@ -34,6 +35,7 @@ struct CbpArgs {
   int64_t xsb, xsn, xsc, zsb, zsn, zsc, vsb, vsn, vsc, dxsb, dxsn, dxsc;
   int B, Nb, Ci, Co, L, act;
   float slope;
+  InNorm in;          // X given as the previous block's stored pre-activation (gamma == nullptr: X as it is)
   // workspace
   CbpChan* chan;      // [B][Co]
   float* p0;          // [B][Co]
@@ -95,6 +97,7 @@ struct GramArgs {
   int64_t xsb, xsn, xsc;
   int Nb, Ci, L, tiles_k, chunks;
   uint32_t x_extent;
+  InNorm in;          // X given as the previous block's stored pre-activation (gamma == nullptr: X as it is)
 };
 
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gram_kernel(GramArgs p) {
@@ -107,6 +110,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gram_kernel(GramArgs p) {
   const int total = p.Nb * p.tiles_k;
   const int t0 = (int)((int64_t)total * chunk / p.chunks), t1 = (int)((int64_t)total * (chunk + 1) / p.chunks);
   const int row = t >> 5, piece = t & 31;                // 8 rows x 32 pieces per pass, 16 passes
+  __shared__ float4 icn[128];                            // the input block's BatchNorm constants, if X is a pre-activation
+  const bool xin = p.in.gamma != nullptr;
+  if (xin) {
+    if (t < 128) icn[t] = t < p.Ci ? in_norm_consts(p.in, (int64_t)b * p.Ci + t) : make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+  }
   uint2 q[16];
   auto load = [&](int tile) {
     const int n = tile / p.tiles_k, l = (tile - n * p.tiles_k) * GPTS + piece * 4;
@@ -130,6 +139,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gram_kernel(GramArgs p) {
   load(t0);
   for (int tile = t0; tile < t1; ++tile) {
     unsigned char* buf = smem[(tile - t0) & 1];
+    if (xin) {
+      const int nn = tile / p.tiles_k;
+      const bool ok = (tile - nn * p.tiles_k) * GPTS + piece * 4 + 4 <= p.L;
+#pragma unroll
+      for (int h = 0; h < 16; ++h) q[h] = in_norm_apply4(q[h], icn[row + 8 * h], ok, p.in.act, p.in.slope);
+    }
 #pragma unroll
     for (int h = 0; h < 16; ++h) *reinterpret_cast<uint2*>(buf + (row + 8 * h) * GP + piece * 8) = q[h];
     __syncthreads();                                     // the other buffer was last read one step ago
@@ -190,8 +205,8 @@ size_t gram_partial_bytes(int B, int Nb, int Ci, int L) { return (size_t)gram_ch
 
 // XX[b][ci][cj] for all models; `partial` holds gram_partial_bytes
 int gram_launch(int B, int Nb, int Ci, int L, const void* X, const int64_t xs[4], float* XX, float* partial,
-                uint32_t x_extent, hipStream_t st) {
-  GramArgs g{(const bf16_raw*)X, partial, XX, xs[0], xs[1], xs[2], Nb, Ci, L, (L + 127) / 128, gram_chunks(B, Nb, L), x_extent};
+                uint32_t x_extent, const InNorm& in, hipStream_t st) {
+  GramArgs g{(const bf16_raw*)X, partial, XX, xs[0], xs[1], xs[2], Nb, Ci, L, (L + 127) / 128, gram_chunks(B, Nb, L), x_extent, in};
   hipLaunchKernelGGL(gram_kernel, dim3((unsigned)g.chunks, (unsigned)B), dim3(GEMM_THREADS), 0, st, g);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   const int64_t count = (int64_t)B * Ci * Ci;
@@ -318,6 +333,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void cbp_dx_kernel(CbpArgs p) {
   __shared__ unsigned char hit_q[1024];                // channel, column inside the tile, gradient value;
   __shared__ float hit_s[1024];                        // sorted by column, channel order inside a column
   __shared__ float sxs[256];
+  __shared__ float4 icn[KT];                           // the input block's BatchNorm constants, if X is a pre-activation
   unsigned char* Xs = smem;
   unsigned char* Gs = smem + TILE;
 
@@ -357,6 +373,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void cbp_dx_kernel(CbpArgs p) {
         const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? (uint32_t)k * ldb + (uint32_t)c * 2u : PF_OOB), 0, 0);
         q[s][j] = make_uint2(v.x, v.y);
       }
+    if (p.in.gamma) {                    // X is a stored pre-activation: the block's activated output is formed here
+      for (int k = t; k < KT; k += GEMM_THREADS)
+        icn[k] = k < p.Ci ? in_norm_consts(p.in, (int64_t)b * p.Ci + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < SUB; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) q[s][j] = in_norm_apply4(q[s][j], icn[s * 32 + 4 * kq + j], c + 4 <= p.L, p.in.act, p.in.slope);
+    }
     // the tile's hit list rides along with the tile loads
     const uint32_t key0 = t < nh ? skey[t] : 0u;
     const float sv0 = t < nh ? sval[t] : 0.f;
@@ -637,6 +662,7 @@ struct FbpArgs {
   float* SXpart;                           // [B][Nb][tiles][2][Ci]
   float* pmax; int* pidx;                  // [B][Nb][tiles][Co]
   uint32_t x_extent, w_extent;
+  InNorm in;                               // X given as the previous block's stored pre-activation (gamma == nullptr: X as it is)
 };
 
 // One workgroup owns a 128-point slice of one sample; each wavefront keeps its half of the X tile
@@ -658,6 +684,7 @@ __global__ __launch_bounds__(GEMM_THREADS, FBP_OCC) void fbp_main_kernel(FbpArgs
   __shared__ __attribute__((aligned(16))) unsigned char smem[XTILE > 2 * WTILE ? XTILE : 2 * WTILE];
   __shared__ float pm_v[2][2][RT];                     // [step parity][point half][channel]
   __shared__ int pm_p[2][2][RT];
+  __shared__ float4 icn[KT];                           // the input block's BatchNorm constants, if X is a pre-activation
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -712,6 +739,15 @@ __global__ __launch_bounds__(GEMM_THREADS, FBP_OCC) void fbp_main_kernel(FbpArgs
         const pf_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(ok ? (uint32_t)k * ldb + (uint32_t)c * 2u : PF_OOB), 0, 0);
         q[s][j] = make_uint2(v.x, v.y);
       }
+    if (p.in.gamma) {                    // X is a stored pre-activation: the block's activated output is formed here
+      for (int k = t; k < KT; k += GEMM_THREADS)
+        icn[k] = k < p.Ci ? in_norm_consts(p.in, (int64_t)b * p.Ci + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < SUB; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) q[s][j] = in_norm_apply4(q[s][j], icn[s * 32 + 4 * kq + j], c + 4 <= p.L, p.in.act, p.in.slope);
+    }
 #pragma unroll
     for (int s = 0; s < SUB; ++s) {
       const uint32_t a0 = q[s][0].x, a1 = q[s][1].x, a2 = q[s][2].x, a3 = q[s][3].x;
@@ -936,7 +972,11 @@ __global__ __launch_bounds__(256) void fbp_finish_kernel(FbpArgs p, int tiles) {
     const bf16_raw* x0 = p.X + b * p.xsb + n * p.xsn;
     const bf16_raw* w = p.W + (int64_t)k * p.Ci;
     float acc = 0.f;
-    for (int ci = 0; ci < p.Ci; ++ci) acc = fmaf(bf16_to_f32(w[ci]), bf16_to_f32(x0[ci * p.xsc]), acc);
+    for (int ci = 0; ci < p.Ci; ++ci) {
+      float xv = bf16_to_f32(x0[ci * p.xsc]);
+      if (p.in.gamma) xv = bf16_to_f32(f32_to_bf16(in_norm_one(xv, in_norm_consts(p.in, (int64_t)b * p.Ci + ci), p.in.act, p.in.slope)));
+      acc = fmaf(bf16_to_f32(w[ci]), xv, acc);
+    }
     at = 0;
     z = acc + bias;
     pre = fmaf(scale, z - mean, beta);
@@ -1005,12 +1045,12 @@ size_t hfta_conv1x1_bn_maxpool_bwd_workspace_bytes(int B, int Nb, int Ci, int Co
   return cbp_layout(B, Nb, Ci, Co, L).total;
 }
 
-int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
-                                const void* W, const void* bias, const void* Z, const int64_t zs[4], const float* zhit,
-                                const float* saved_moments, const void* dV, const int32_t* idx, const int64_t vs[3],
-                                const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
-                                void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
-                                int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+static int cbp_run(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                   const void* W, const void* bias, const void* Z, const int64_t zs[4], const float* zhit,
+                   const float* saved_moments, const void* dV, const int32_t* idx, const int64_t vs[3],
+                   const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
+                   void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
+                   int act, float act_slope, void* workspace, size_t ws_bytes, void* stream, const InNorm& in) {
   if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !W || !dV ||
       !idx || !vs || !gamma || !beta || !save_mean || !save_invstd || !dX || !dxs || !dW || !dgamma || !dbeta)
     return HFTA_EINVAL;
@@ -1027,6 +1067,7 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   hipStream_t st = as_stream(stream);
 
   CbpArgs a{};
+  a.in = in;
   a.X = (const bf16_raw*)X; a.W = (const bf16_raw*)W; a.bias = (const bf16_raw*)bias; a.Z = (const bf16_raw*)Z;
   a.dV = (const bf16_raw*)dV; a.idx = idx; a.zhit = zhit;
   a.gamma = gamma; a.beta = beta; a.save_mean = save_mean; a.save_invstd = save_invstd;
@@ -1051,7 +1092,7 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   hipLaunchKernelGGL(cbp_coef_kernel, dim3((unsigned)Co, (unsigned)B), dim3(64), 0, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   if (!saved_moments) {          // Gram matrix of the layer input: XX[b] = sum_{n,l} x x^T
-    const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, st);
+    const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, in, st);
     if (rc != HFTA_OK) return rc;
   }
   const int T32 = (Ci + 31) / 32;
@@ -1081,12 +1122,12 @@ size_t hfta_conv1x1_bn_maxpool_fwd_workspace_bytes(int B, int Nb, int Ci, int Co
   return fbp_layout(B, Nb, Ci, Co, L, true).total;
 }
 
-int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
-                                const void* W, const void* bias, const float* gamma, const float* beta, float eps,
-                                float momentum, float* running_mean, float* running_var, float* save_mean,
-                                float* save_invstd, void* V, int32_t* idx, const int64_t vs[3], float* zhit,
-                                float* saved_moments, int act, float act_slope, void* workspace, size_t ws_bytes,
-                                void* stream) {
+static int fbp_run(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                   const void* W, const void* bias, const float* gamma, const float* beta, float eps,
+                   float momentum, float* running_mean, float* running_var, float* save_mean,
+                   float* save_invstd, void* V, int32_t* idx, const int64_t vs[3], float* zhit,
+                   float* saved_moments, int act, float act_slope, void* workspace, size_t ws_bytes,
+                   void* stream, const InNorm& in) {
   if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !W || !gamma || !beta ||
       !save_mean || !save_invstd || !V || !idx || !vs || !zhit || !(eps >= 0.f))
     return HFTA_EINVAL;
@@ -1104,6 +1145,7 @@ int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   hipStream_t st = as_stream(stream);
 
   FbpArgs a{};
+  a.in = in;
   a.X = (const bf16_raw*)X; a.W = (const bf16_raw*)W; a.bias = (const bf16_raw*)bias; a.gamma = gamma; a.beta = beta;
   a.running_mean = running_mean; a.running_var = running_var; a.save_mean = save_mean; a.save_invstd = save_invstd;
   a.V = (bf16_raw*)V; a.idx = idx; a.zhit = zhit;
@@ -1116,7 +1158,7 @@ int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   a.SXpart = (float*)(ws + lay.SXpart); a.pmax = (float*)(ws + lay.pmax); a.pidx = (int*)(ws + lay.pidx);
   a.x_extent = (uint32_t)x_ext; a.w_extent = (uint32_t)w_ext;
 
-  const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, st);
+  const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, in, st);
   if (rc != HFTA_OK) return rc;
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
   if (Ci <= 64) hipLaunchKernelGGL((fbp_main_kernel<64, FBP_RT>), grid, dim3(GEMM_THREADS), 0, st, a);
@@ -1129,6 +1171,59 @@ int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   hipLaunchKernelGGL(fbp_finish_kernel, dim3((unsigned)((Co + 255) / 256), (unsigned)Nb, (unsigned)B), dim3(256), 0, st, a,
                      (int)grid.x);
   return launch_status();
+}
+
+
+int hfta_conv1x1_bn_maxpool_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                                const void* W, const void* bias, const float* gamma, const float* beta, float eps,
+                                float momentum, float* running_mean, float* running_var, float* save_mean,
+                                float* save_invstd, void* V, int32_t* idx, const int64_t vs[3], float* zhit,
+                                float* saved_moments, int act, float act_slope, void* workspace, size_t ws_bytes,
+                                void* stream) {
+  return fbp_run(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
+                 save_invstd, V, idx, vs, zhit, saved_moments, act, act_slope, workspace, ws_bytes, stream, InNorm{});
+}
+
+int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                                const void* W, const void* bias, const void* Z, const int64_t zs[4], const float* zhit,
+                                const float* saved_moments, const void* dV, const int32_t* idx, const int64_t vs[3],
+                                const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
+                                void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
+                                int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+  return cbp_run(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, zhit, saved_moments, dV, idx, vs, gamma, beta, save_mean,
+                 save_invstd, dX, dxs, dW, dbias, dgamma, dbeta, act, act_slope, workspace, ws_bytes, stream, InNorm{});
+}
+
+// The same operator with X given as the previous block's stored pre-activation and that block's BatchNorm
+// constants: every kernel that reads X forms the block's activated output on load.
+int hfta_conv1x1_bn_maxpool_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* Xpre,
+                                        const int64_t xs[4], const float* in_gamma, const float* in_beta,
+                                        const float* in_mean, const float* in_invstd, int in_act, float in_slope,
+                                        const void* W, const void* bias, const float* gamma, const float* beta, float eps,
+                                        float momentum, float* running_mean, float* running_var, float* save_mean,
+                                        float* save_invstd, void* V, int32_t* idx, const int64_t vs[3], float* zhit,
+                                        float* saved_moments, int act, float act_slope, void* workspace, size_t ws_bytes,
+                                        void* stream) {
+  if (!in_gamma || !in_beta || !in_mean || !in_invstd) return HFTA_EINVAL;
+  const InNorm in{in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope};
+  if (!in_norm_valid(in)) return HFTA_EUNSUPPORTED;
+  return fbp_run(B, Nb, Ci, Co, L, dtype, Xpre, xs, W, bias, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
+                 save_invstd, V, idx, vs, zhit, saved_moments, act, act_slope, workspace, ws_bytes, stream, in);
+}
+
+int hfta_conv1x1_bn_maxpool_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* Xpre,
+                                        const int64_t xs[4], const float* in_gamma, const float* in_beta,
+                                        const float* in_mean, const float* in_invstd, int in_act, float in_slope,
+                                        const void* W, const void* bias, const float* zhit, const float* saved_moments,
+                                        const void* dV, const int32_t* idx, const int64_t vs[3], const float* gamma,
+                                        const float* beta, const float* save_mean, const float* save_invstd, void* dX,
+                                        const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act,
+                                        float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+  if (!in_gamma || !in_beta || !in_mean || !in_invstd) return HFTA_EINVAL;
+  const InNorm in{in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope};
+  if (!in_norm_valid(in)) return HFTA_EUNSUPPORTED;
+  return cbp_run(B, Nb, Ci, Co, L, dtype, Xpre, xs, W, bias, nullptr, nullptr, zhit, saved_moments, dV, idx, vs, gamma, beta,
+                 save_mean, save_invstd, dX, dxs, dW, dbias, dgamma, dbeta, act, act_slope, workspace, ws_bytes, stream, in);
 }
 
 }  // extern "C"

@@ -1029,6 +1029,60 @@ def test_conv1x1_bn_maxpool_bwd_fused(hb, B, Nb, Ci, Co, L, act):
     assert torch.equal(dG, dG2) or np.abs(host(dG) - host(dG2)).max() <= 1e-5 * max(np.abs(rdg).max(), sc * 1e-2)
 
 
+@pytest.mark.parametrize("B,Nb,Ci,Co,L,in_act,saved", [(2, 3, 128, 1024, 644, 1, True), (2, 4, 64, 200, 260, 2, False),
+                                                        (3, 2, 24, 72, 132, 1, True)])
+def test_conv1x1_bn_maxpool_prenorm(hb, B, Nb, Ci, Co, L, in_act, saved):
+    """The one-operator tail at the end of a chain whose activated tensors are not stored: its input given as
+    the previous block's pre-activation and BatchNorm constants must give, bit for bit, what the plain
+    operator gives on that block's stored output (forward and backward; with and without the moments the
+    forward saved), the plain operator being the one checked against the oracle above."""
+    dtype = "bf16"
+    print(f"conv+bn+pool prenorm B={B} Nb={Nb} Ci={Ci} Co={Co} L={L} in_act={in_act} saved={saved}", flush=True)
+    xpre = hi.snap(hi.normal(151, (Nb, B * Ci, L)) * 1.5 + 0.4, dtype)
+    gi = (hi.normal(152, (B * Ci,)) * 0.5 + 1.0).astype(np.float32)
+    bi = (hi.normal(153, (B * Ci,)) * 0.3).astype(np.float32)
+    w = hi.normal(154, (B * Co, Ci), dtype, 1.0 / np.sqrt(Ci))
+    bias = hi.normal(155, (B * Co,), dtype, 0.1)
+    g = (hi.normal(156, (B * Co,)) * 0.3 + 1.0).astype(np.float32)
+    g[::3] = -np.abs(g[::3])
+    bt = (hi.normal(157, (B * Co,)) * 0.3).astype(np.float32)
+    bt[1::7] = -6.0                                     # rows clipped flat by the ReLU: the rare path that re-reads X at point 0
+    dv = hi.normal(158, (B, Nb, Co), dtype)
+    sx, vs = conv_strides(B, Ci, L), (Nb * Co, Co, 1)
+    f32 = torch.float32
+    Xp, Gi, Bi_, W, Bs, G, Bt, dV = dev(xpre, dtype), dev(gi), dev(bi), dev(w, dtype), dev(bias, dtype), dev(g), dev(bt), dev(dv, dtype)
+    MI, II, X = empty((B * Ci,), f32), empty((B * Ci,), f32), empty((Nb, B * Ci, L), dtype)
+    hb.bn_fwd(B, Nb, Ci, L, DT[dtype], Xp, sx, Gi, Bi_, 1e-5, 0.1, None, None, MI, II, X, sx, in_act, 0.2)
+    nws = max(hb.conv1x1_bn_maxpool_fwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype]),
+              hb.conv1x1_bn_maxpool_bwd_workspace_bytes(B, Nb, Ci, Co, L, DT[dtype]))
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    out = {}
+    for kind in ("plain", "prenorm"):
+        SM, SI = empty((B * Co,), f32), empty((B * Co,), f32)
+        RM, RV = dev(np.zeros(B * Co, np.float32)), dev(np.ones(B * Co, np.float32))
+        V, I = empty((B, Nb, Co), dtype), torch.empty(B, Nb, Co, dtype=torch.int32, device="cuda")
+        ZH = empty((B, Nb, Co), f32)
+        SAV = empty((hb.conv1x1_bn_maxpool_saved_floats(B, Ci, Co),), f32) if saved else None
+        dX, dW, db = empty((Nb, B * Ci, L), dtype), empty((B * Co, Ci), f32), empty((B * Co,), f32)
+        dG, dB = empty((B * Co,), f32), empty((B * Co,), f32)
+        ws.fill_(0x5a)
+        if kind == "plain":
+            hb.conv1x1_bn_maxpool_fwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bs, G, Bt, 1e-5, 0.1, RM, RV, SM, SI, V, I, vs, ZH, SAV,
+                                      1, 0.0, ws)
+            hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bs, None, None, ZH, SAV, dV, I, vs, G, Bt, SM, SI, dX,
+                                      sx, dW, db, dG, dB, 1, 0.0, ws)
+        else:
+            hb.conv1x1_bn_maxpool_prenorm_fwd(B, Nb, Ci, Co, L, DT[dtype], Xp, sx, Gi, Bi_, MI, II, in_act, 0.2, W, Bs, G, Bt, 1e-5,
+                                              0.1, RM, RV, SM, SI, V, I, vs, ZH, SAV, 1, 0.0, ws)
+            hb.conv1x1_bn_maxpool_prenorm_bwd(B, Nb, Ci, Co, L, DT[dtype], Xp, sx, Gi, Bi_, MI, II, in_act, 0.2, W, Bs, ZH, SAV, dV, I,
+                                              vs, G, Bt, SM, SI, dX, sx, dW, db, dG, dB, 1, 0.0, ws)
+        out[kind] = dict(V=V, I=I, ZH=ZH, SM=SM, SI=SI, RM=RM, RV=RV, dX=dX, dW=dW, db=db, dG=dG, dB=dB)
+    for k, v in out["plain"].items():
+        assert torch.equal(v, out["prenorm"][k]), f"{k} differs from the plain operator on the stored activated tensor"
+    assert bool(torch.isfinite(out["prenorm"]["dX"].float()).all()) and float(out["prenorm"]["dW"].abs().max()) > 0
+
+
 @pytest.mark.parametrize("B,Nb,Ci,Co,L,act", [(2, 5, 16, 40, 300, 1), (2, 3, 128, 136, 260, 1), (3, 4, 64, 72, 132, 2),
                                                (2, 3, 8, 1024, 8, 0), (1, 2, 128, 300, 1156, 1)])
 def test_conv1x1_bn_maxpool_fwd_bwd_one_operator(hb, B, Nb, Ci, Co, L, act):
