@@ -41,7 +41,7 @@ class Tracer:
                      "attention_fwd", "attention_bwd", "embedding_fwd", "embedding_bwd", "softmax_xent", "softmax_xent_rows",
                      "point_transform_fwd", "point_transform_bwd",
                      "conv1x1_bn_maxpool_bwd", "conv1x1_bn_fwd", "conv1x1_bn_bwd", "conv1x1_bn_prenorm_fwd",
-                     "conv1x1_bn_prenorm_bwd")
+                     "conv1x1_bn_prenorm_bwd", "conv1x1_bn_maxpool_prenorm_fwd", "conv1x1_bn_maxpool_prenorm_bwd")
 
     def __init__(self, hb, torch):
         self._hb, self._torch = hb, torch
@@ -181,10 +181,11 @@ def kernel_label(name, a):
         return k + "(dW)+splitk_reduce_kernel"
     if name in ("bn_fwd_maxpool", "bn_bwd_maxpool"):
         return name + "_kernel"
-    if name == "conv1x1_bn_maxpool_fwd":
+    if name in ("conv1x1_bn_maxpool_fwd", "conv1x1_bn_maxpool_prenorm_fwd"):      # the same kernels, the input normalised on load
         return "conv1x1_bn_maxpool_fwd: fbp_main_kernel + gram_kernel + 4 small"
-    if name == "conv1x1_bn_maxpool_bwd":
-        return "conv1x1_bn_maxpool_bwd: cbp_dx_kernel + 5 small" + ("" if a[13] is not None else " + gram_kernel")
+    if name in ("conv1x1_bn_maxpool_bwd", "conv1x1_bn_maxpool_prenorm_bwd"):
+        saved = a[13] if name == "conv1x1_bn_maxpool_bwd" else a[17]
+        return "conv1x1_bn_maxpool_bwd: cbp_dx_kernel + 5 small" + ("" if saved is not None else " + gram_kernel")
     return {"maxpool_points": "maxpool_fwd_kernel", "maxpool_points_bwd": "maxpool_bwd_kernel",
             "adam_step_multi": "adam_multi_kernel"}[name]
 
@@ -243,12 +244,13 @@ def algorithmic_flops(name, a):
     if name in ("attention_fwd", "attention_bwd"):      # 2 (forward) / 4 (backward) products of S x S x d per head
         B, N, S, E, H = a[:5]
         return (2 if name == "attention_fwd" else 4) * 2.0 * B * N * S * S * E
-    if name == "conv1x1_bn_maxpool_fwd":      # the Ci -> Co product (its output is reduced, never stored) + the Gram matrix
+    if name in ("conv1x1_bn_maxpool_fwd", "conv1x1_bn_maxpool_prenorm_fwd"):      # the Ci -> Co product (its output is reduced, never stored) + the Gram matrix
         B, Nb, Ci, Co, L = a[:5]
         return 2.0 * B * Nb * Ci * (Co + Ci) * L
-    if name == "conv1x1_bn_maxpool_bwd":      # the Ci -> Ci product of the data gradient (+ the Gram matrix if not saved)
+    if name in ("conv1x1_bn_maxpool_bwd", "conv1x1_bn_maxpool_prenorm_bwd"):      # the Ci -> Ci product of the data gradient (+ the Gram matrix if not saved)
         B, Nb, Ci, Co, L = a[:5]
-        return (2.0 if a[13] is not None else 4.0) * B * Nb * Ci * Ci * L
+        saved = a[13] if name == "conv1x1_bn_maxpool_bwd" else a[17]
+        return (2.0 if saved is not None else 4.0) * B * Nb * Ci * Ci * L
     if name in ("conv2d_grouped_fwd", "conv2d_grouped_bwd"):
         B, Nb, Ci, Co, H, W, kh, kw, st, pad = a[:10]
         Ho, Wo = (H + 2 * pad - kh) // st + 1, (W + 2 * pad - kw) // st + 1
@@ -289,10 +291,10 @@ def algorithmic_bytes(name, a):
         if a[11] is not None:          # dX = W^T dY: dY and W in, dX out
             return (B * Nb * (Ci + Co) * L + B * Co * Ci) * _es(dt)
         return B * Nb * (Ci + Co) * L * _es(dt) + B * Co * Ci * 4      # dW (fp32) = dY X^T
-    if name == "conv1x1_bn_maxpool_fwd":      # x in, W in, pooled + argmax + z at the argmax out
+    if name in ("conv1x1_bn_maxpool_fwd", "conv1x1_bn_maxpool_prenorm_fwd"):      # x in, W in, pooled + argmax + z at the argmax out
         B, Nb, Ci, Co, L, dt = a[:6]
         return B * Nb * Ci * L * _es(dt) + B * Co * Ci * _es(dt) + B * Nb * Co * (_es(dt) + 4 + 4)
-    if name == "conv1x1_bn_maxpool_bwd":      # x in, dx out, W in, dW (fp32) out, pooled gradient + argmax in
+    if name in ("conv1x1_bn_maxpool_bwd", "conv1x1_bn_maxpool_prenorm_bwd"):      # x in, dx out, W in, dW (fp32) out, pooled gradient + argmax in
         B, Nb, Ci, Co, L, dt = a[:6]
         return 2 * B * Nb * Ci * L * _es(dt) + B * Co * Ci * (_es(dt) + 4) + B * Nb * Co * (_es(dt) + 4 + _es(dt))
     if name == "linear_bwd":

@@ -320,6 +320,14 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype,
                 float* save_mean, float* save_invstd,
                 void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
 
+/* Normalisation with GIVEN statistics (row "BatchNorm1d"): Y = act(gamma (X - mean) invstd + beta) with
+ * mean, invstd [B][C] fp32 as hfta_bn_fwd saved them: the second pass of hfta_bn_fwd alone, bit-identical
+ * to what it stored.  For a consumer that dropped an activated tensor (hfta_conv1x1_bn_prenorm_fwd) and
+ * wants it back, e.g. to recompute or to inspect it.  Conv layouts (stride_l == 1); nothing is updated. */
+int hfta_bn_apply_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4],
+                      const float* gamma, const float* beta, const float* mean, const float* invstd,
+                      void* Y, const int64_t ys[4], int act, float act_slope, void* stream);
+
 /* Evaluation mode of the same rows (the fused operator keeps every argument of the single-model one,
  * its training flag included; with the flag off the running estimates replace the batch statistics):
  *   y = act(gamma (x - running_mean) / sqrt(running_var + eps) + beta); nothing is updated or saved.
@@ -445,7 +453,13 @@ int hfta_conv1x1_bn_maxpool_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
  * on load with the arithmetic of hfta_bn_fwd (see hfta_conv1x1_bn_prenorm_fwd).  Results are
  * bit-identical to storing X and calling the plain pair.  Shapes, workspaces, other arguments and
  * errors as the plain pair; the backward call takes the convolution output at the argmax (zhit),
- * not Z; dX is the gradient with respect to X. */
+ * not Z; dX is the gradient with respect to X.
+ * Xact (optional, with strides xas[4], stride_l == 1, 8-byte aligned, strides % 4 == 0): the forward
+ * operator's first kernel, which reads every element of Xpre exactly once, also writes X there, and
+ * the operator's other kernels read X from it as the plain operator does.  The backward is then the
+ * plain hfta_conv1x1_bn_maxpool_bwd on Xact.  This trades the on-load arithmetic in the two
+ * kernels bound by their matrix products for one more tensor write; the normalisation pass of
+ * the previous block (a read and a write of the tensor) is saved either way. */
 int hfta_conv1x1_bn_maxpool_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                                         const void* Xpre, const int64_t xs[4],
                                         const float* in_gamma, const float* in_beta, const float* in_mean,
@@ -454,7 +468,8 @@ int hfta_conv1x1_bn_maxpool_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, in
                                         float eps, float momentum, float* running_mean, float* running_var,
                                         float* save_mean, float* save_invstd,
                                         void* V, int32_t* idx, const int64_t vs[3], float* zhit, float* saved_moments,
-                                        int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
+                                        int act, float act_slope, void* Xact, const int64_t xas[4],
+                                        void* workspace, size_t ws_bytes, void* stream);
 int hfta_conv1x1_bn_maxpool_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                                         const void* Xpre, const int64_t xs[4],
                                         const float* in_gamma, const float* in_beta, const float* in_mean,

@@ -70,13 +70,14 @@ _SIGS = {
     "hfta_conv2d_grouped_bwd_workspace_bytes": (_sz, [_i] * 11),
     "hfta_conv2d_grouped_bwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "hfta_bn_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
+    "hfta_bn_apply_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
     "hfta_bn_eval_fwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _p, _f, _p, _s4, _i, _f, _p]),
     "hfta_bn_bwd": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_bn_fwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _f, _f, _p, _p, _p, _p, _p, _p, _s4, _i, _f, _p]),
     "hfta_bn_bwd_maxpool": (_i, [_i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _i, _f, _p]),
     "hfta_conv1x1_bn_maxpool_bwd_workspace_bytes": (_sz, [_i] * 6),
     "hfta_conv1x1_bn_maxpool_bwd": (_i, [_i] * 6 + [_p] * 21 + [_i, _f, _p, _sz, _p]),
-    "hfta_conv1x1_bn_maxpool_prenorm_fwd": (_i, [_i] * 6 + [_p] * 6 + [_i, _f] + [_p] * 4 + [_f, _f] + [_p] * 9 + [_i, _f, _p, _sz, _p]),
+    "hfta_conv1x1_bn_maxpool_prenorm_fwd": (_i, [_i] * 6 + [_p] * 6 + [_i, _f] + [_p] * 4 + [_f, _f] + [_p] * 9 + [_i, _f, _p, _s4, _p, _sz, _p]),
     "hfta_conv1x1_bn_maxpool_prenorm_bwd": (_i, [_i] * 6 + [_p] * 6 + [_i, _f] + [_p] * 17 + [_i, _f, _p, _sz, _p]),
     "hfta_point_transform_fwd": (_i, [_i] * 6 + [_p] * 6),
     "hfta_point_transform_bwd": (_i, [_i] * 6 + [_p] * 9),
@@ -318,6 +319,11 @@ def bn_fwd(B, Nb, C_, L, dtype, X, xs, gamma, beta, eps, momentum, running_mean,
                             _strides(ys), act, act_slope, _stream(stream)), "hfta_bn_fwd")
 
 
+def bn_apply_fwd(B, Nb, C_, L, dtype, X, xs, gamma, beta, mean, invstd, Y, ys, act=ACT_NONE, act_slope=0.0, stream=None):
+    _check(_lib.hfta_bn_apply_fwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(invstd),
+                                  _ptr(Y), _strides(ys), act, act_slope, _stream(stream)), "hfta_bn_apply_fwd")
+
+
 def bn_eval_fwd(B, Nb, C_, L, dtype, X, xs, gamma, beta, running_mean, running_var, eps, Y, ys, act=ACT_NONE,
                 act_slope=0.0, stream=None):
     _check(_lib.hfta_bn_eval_fwd(B, Nb, C_, L, dtype, _ptr(X), _strides(xs), _ptr(gamma), _ptr(beta), _ptr(running_mean),
@@ -366,13 +372,15 @@ def conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, zhit,
 
 def conv1x1_bn_maxpool_prenorm_fwd(B, Nb, Ci, Co, L, dtype, Xpre, xs, in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope, W,
                                    bias, gamma, beta, eps, momentum, running_mean, running_var, save_mean, save_invstd, V, idx,
-                                   vs, zhit, saved_moments, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None):
+                                   vs, zhit, saved_moments, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None, Xact=None,
+                                   xas=None):
     wp, wb = _ws(workspace)
     _check(_lib.hfta_conv1x1_bn_maxpool_prenorm_fwd(B, Nb, Ci, Co, L, dtype, _ptr(Xpre), _strides(xs), _ptr(in_gamma),
                                                     _ptr(in_beta), _ptr(in_mean), _ptr(in_invstd), in_act, in_slope, _ptr(W),
                                                     _ptr(bias), _ptr(gamma), _ptr(beta), eps, momentum, _ptr(running_mean),
                                                     _ptr(running_var), _ptr(save_mean), _ptr(save_invstd), _ptr(V), _ptr(idx),
-                                                    _strides(vs, 3), _ptr(zhit), _ptr(saved_moments), act, act_slope, wp, wb,
+                                                    _strides(vs, 3), _ptr(zhit), _ptr(saved_moments), act, act_slope, _ptr(Xact),
+                                                    _strides(xas), wp, wb,
                                                     _stream(stream)), "hfta_conv1x1_bn_maxpool_prenorm_fwd")
 
 

@@ -95,6 +95,34 @@ __global__ __launch_bounds__(NT) void bn_fwd_conv_kernel(BnFwdArgs p) {
 
 
 
+// Normalisation with given statistics (the forward kernel's second pass alone): what a consumer that
+// normalises on load computes, written out.
+template <typename T, int VEC, int NT>
+__global__ __launch_bounds__(NT) void bn_apply_conv_kernel(BnFwdArgs p) {
+  const int c = blockIdx.x, b = blockIdx.y, k = b * p.C + c;
+  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
+  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
+  const int chunks = p.L / VEC;
+  const float mean = p.save_mean[k], invstd = p.save_invstd[k], g = p.gamma[k], bt = p.beta[k];
+  for (RowWalk w(chunks, NT); w.n < p.Nb;) {
+    float v[BN_UNROLL][VEC];
+    int n[BN_UNROLL], ch[BN_UNROLL];
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u) {
+      n[u] = w.n; ch[u] = w.ch;
+      load_vec<T, VEC>(n[u] < p.Nb ? x + n[u] * p.xsn + ch[u] * VEC : x, v[u]);
+      w.step();
+    }
+#pragma unroll
+    for (int u = 0; u < BN_UNROLL; ++u)
+      if (n[u] < p.Nb) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[u][e] = apply_act(fmaf(g, (v[u][e] - mean) * invstd, bt), p.act, p.slope);
+        store_vec<T, VEC>(y + n[u] * p.ysn + ch[u] * VEC, v[u]);
+      }
+  }
+}
+
 // The same forward with its statistics taken from partial sums that the producing convolution left
 // behind (sums of (x - shift) and (x - shift)^2 per slice, shift = the channel's conv bias or 0):
 // the channel is read once, for the normalisation.
@@ -514,6 +542,29 @@ int hfta_bn_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int
   if (dtype == HFTA_BF16) { if (v4) HFTA_BN_FWD(bf16_raw, 4); else HFTA_BN_FWD(bf16_raw, 1); }
   else { if (v4) HFTA_BN_FWD(float, 4); else HFTA_BN_FWD(float, 1); }
 #undef HFTA_BN_FWD
+  return launch_status();
+}
+
+int hfta_bn_apply_fwd(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
+                      const float* beta, const float* mean, const float* invstd, void* Y, const int64_t ys[4], int act,
+                      float act_slope, void* stream) {
+  if (B <= 0 || Nb <= 0 || C <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !gamma || !beta || !mean || !invstd ||
+      !Y || !ys)
+    return HFTA_EINVAL;
+  if (act != HFTA_ACT_NONE && act != HFTA_ACT_RELU && act != HFTA_ACT_LEAKY) return HFTA_EUNSUPPORTED;
+  if (B > 65535 || layout_kind(xs, L) != 1 || layout_kind(ys, L) != 1) return HFTA_EUNSUPPORTED;
+  BnFwdArgs a{X, Y, gamma, beta, nullptr, nullptr, const_cast<float*>(mean), const_cast<float*>(invstd),
+              xs[0], xs[1], xs[2], ys[0], ys[1], ys[2], Nb, C, L, act, 0.f, 0.f, act_slope};
+  hipStream_t st = as_stream(stream);
+  const dim3 grid((unsigned)C, (unsigned)B);
+  const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
+  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
+#define HFTA_BN_APPLY(T, V) \
+  do { if (big) hipLaunchKernelGGL((bn_apply_conv_kernel<T, V, 1024>), grid, dim3(1024), 0, st, a); \
+       else hipLaunchKernelGGL((bn_apply_conv_kernel<T, V, 256>), grid, dim3(256), 0, st, a); } while (0)
+  if (dtype == HFTA_BF16) { if (v4) HFTA_BN_APPLY(bf16_raw, 4); else HFTA_BN_APPLY(bf16_raw, 1); }
+  else { if (v4) HFTA_BN_APPLY(float, 4); else HFTA_BN_APPLY(float, 1); }
+#undef HFTA_BN_APPLY
   return launch_status();
 }
 

@@ -98,6 +98,8 @@ struct GramArgs {
   int Nb, Ci, L, tiles_k, chunks;
   uint32_t x_extent;
   InNorm in;          // X given as the previous block's stored pre-activation (gamma == nullptr: X as it is)
+  bf16_raw* Xact;     // with `in`: where the values formed on load are also written (nullptr: nowhere)
+  int64_t asb, asn, asc;
 };
 
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gram_kernel(GramArgs p) {
@@ -144,6 +146,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gram_kernel(GramArgs p) {
       const bool ok = (tile - nn * p.tiles_k) * GPTS + piece * 4 + 4 <= p.L;
 #pragma unroll
       for (int h = 0; h < 16; ++h) q[h] = in_norm_apply4(q[h], icn[row + 8 * h], ok, p.in.act, p.in.slope);
+      if (p.Xact && ok) {                                  // every element of X passes through exactly one workgroup
+        bf16_raw* o = p.Xact + b * p.asb + nn * p.asn + (tile - nn * p.tiles_k) * GPTS + piece * 4;
+#pragma unroll
+        for (int h = 0; h < 16; ++h)
+          if (row + 8 * h < p.Ci) *reinterpret_cast<uint2*>(o + (row + 8 * h) * p.asc) = q[h];
+      }
     }
 #pragma unroll
     for (int h = 0; h < 16; ++h) *reinterpret_cast<uint2*>(buf + (row + 8 * h) * GP + piece * 8) = q[h];
@@ -205,8 +213,9 @@ size_t gram_partial_bytes(int B, int Nb, int Ci, int L) { return (size_t)gram_ch
 
 // XX[b][ci][cj] for all models; `partial` holds gram_partial_bytes
 int gram_launch(int B, int Nb, int Ci, int L, const void* X, const int64_t xs[4], float* XX, float* partial,
-                uint32_t x_extent, const InNorm& in, hipStream_t st) {
-  GramArgs g{(const bf16_raw*)X, partial, XX, xs[0], xs[1], xs[2], Nb, Ci, L, (L + 127) / 128, gram_chunks(B, Nb, L), x_extent, in};
+                uint32_t x_extent, const InNorm& in, void* Xact, const int64_t xas[4], hipStream_t st) {
+  GramArgs g{(const bf16_raw*)X, partial, XX, xs[0], xs[1], xs[2], Nb, Ci, L, (L + 127) / 128, gram_chunks(B, Nb, L), x_extent, in,
+             (bf16_raw*)Xact, Xact ? xas[0] : 0, Xact ? xas[1] : 0, Xact ? xas[2] : 0};
   hipLaunchKernelGGL(gram_kernel, dim3((unsigned)g.chunks, (unsigned)B), dim3(GEMM_THREADS), 0, st, g);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   const int64_t count = (int64_t)B * Ci * Ci;
@@ -1092,7 +1101,7 @@ static int cbp_run(int B, int Nb, int Ci, int Co, int L, int dtype, const void* 
   hipLaunchKernelGGL(cbp_coef_kernel, dim3((unsigned)Co, (unsigned)B), dim3(64), 0, st, a);
   if (launch_status() != HFTA_OK) return HFTA_ELAUNCH;
   if (!saved_moments) {          // Gram matrix of the layer input: XX[b] = sum_{n,l} x x^T
-    const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, in, st);
+    const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, in, nullptr, nullptr, st);
     if (rc != HFTA_OK) return rc;
   }
   const int T32 = (Ci + 31) / 32;
@@ -1127,9 +1136,9 @@ static int fbp_run(int B, int Nb, int Ci, int Co, int L, int dtype, const void* 
                    float momentum, float* running_mean, float* running_var, float* save_mean,
                    float* save_invstd, void* V, int32_t* idx, const int64_t vs[3], float* zhit,
                    float* saved_moments, int act, float act_slope, void* workspace, size_t ws_bytes,
-                   void* stream, const InNorm& in) {
+                   void* stream, const InNorm& in, void* Xact = nullptr, const int64_t* xas = nullptr) {
   if (B <= 0 || Nb <= 0 || Ci <= 0 || Co <= 0 || L <= 0 || !valid_dtype(dtype) || !X || !xs || !W || !gamma || !beta ||
-      !save_mean || !save_invstd || !V || !idx || !vs || !zhit || !(eps >= 0.f))
+      !save_mean || !save_invstd || !V || !idx || !vs || !zhit || !(eps >= 0.f) || (Xact && !xas))
     return HFTA_EINVAL;
   if ((running_mean == nullptr) != (running_var == nullptr)) return HFTA_EINVAL;
   // the argmax is taken on sign(gamma) z: needs a non-decreasing activation
@@ -1139,6 +1148,9 @@ static int fbp_run(int B, int Nb, int Ci, int Co, int L, int dtype, const void* 
   if (!al(X, 8) || xs[0] % 4 || xs[1] % 4 || xs[2] % 4 || xs[2] <= 0 || !al(W, 16)) return HFTA_EUNSUPPORTED;
   const int64_t x_ext = ((int64_t)(Ci - 1) * xs[2] + L) * 2, w_ext = (int64_t)Co * Ci * 2;
   if (x_ext >= (int64_t)1 << 31 || w_ext >= (int64_t)1 << 31) return HFTA_EUNSUPPORTED;
+  const int64_t xa_ext = Xact ? ((int64_t)(Ci - 1) * xas[2] + L) * 2 : 0;
+  if (Xact && (!al(Xact, 8) || xas[3] != 1 || xas[0] % 4 || xas[1] % 4 || xas[2] % 4 || xas[2] <= 0 || xa_ext >= (int64_t)1 << 31))
+    return HFTA_EUNSUPPORTED;
   const FbpLayout lay = fbp_layout(B, Nb, Ci, Co, L, true);
   if (!workspace || !al(workspace, 256) || ws_bytes < lay.total) return HFTA_EWORKSPACE;
   unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
@@ -1158,8 +1170,12 @@ static int fbp_run(int B, int Nb, int Ci, int Co, int L, int dtype, const void* 
   a.SXpart = (float*)(ws + lay.SXpart); a.pmax = (float*)(ws + lay.pmax); a.pidx = (int*)(ws + lay.pidx);
   a.x_extent = (uint32_t)x_ext; a.w_extent = (uint32_t)w_ext;
 
-  const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, in, st);
+  const int rc = gram_launch(B, Nb, Ci, L, X, xs, a.XX, (float*)(ws + lay.part), a.x_extent, in, Xact, xas, st);
   if (rc != HFTA_OK) return rc;
+  if (Xact) {                    // the first kernel wrote the activated input out: the others read that, as it is
+    a.in = InNorm{};
+    a.X = (const bf16_raw*)Xact; a.xsb = xas[0]; a.xsn = xas[1]; a.xsc = xas[2]; a.x_extent = (uint32_t)xa_ext;
+  }
   dim3 grid((unsigned)((L + 127) / 128), 1, (unsigned)(B * Nb));
   if (Ci <= 64) hipLaunchKernelGGL((fbp_main_kernel<64, FBP_RT>), grid, dim3(GEMM_THREADS), 0, st, a);
   else hipLaunchKernelGGL((fbp_main_kernel<128, FBP_RT>), grid, dim3(GEMM_THREADS), 0, st, a);
@@ -1202,13 +1218,13 @@ int hfta_conv1x1_bn_maxpool_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, in
                                         const void* W, const void* bias, const float* gamma, const float* beta, float eps,
                                         float momentum, float* running_mean, float* running_var, float* save_mean,
                                         float* save_invstd, void* V, int32_t* idx, const int64_t vs[3], float* zhit,
-                                        float* saved_moments, int act, float act_slope, void* workspace, size_t ws_bytes,
-                                        void* stream) {
+                                        float* saved_moments, int act, float act_slope, void* Xact, const int64_t xas[4],
+                                        void* workspace, size_t ws_bytes, void* stream) {
   if (!in_gamma || !in_beta || !in_mean || !in_invstd) return HFTA_EINVAL;
   const InNorm in{in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope};
   if (!in_norm_valid(in)) return HFTA_EUNSUPPORTED;
   return fbp_run(B, Nb, Ci, Co, L, dtype, Xpre, xs, W, bias, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
-                 save_invstd, V, idx, vs, zhit, saved_moments, act, act_slope, workspace, ws_bytes, stream, in);
+                 save_invstd, V, idx, vs, zhit, saved_moments, act, act_slope, workspace, ws_bytes, stream, in, Xact, xas);
 }
 
 int hfta_conv1x1_bn_maxpool_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* Xpre,

@@ -118,6 +118,37 @@ def test_validation_of_the_wider_entry_points(lib):
     assert tail_bwd(dt=0) == lib.EUNSUPPORTED
     assert tail_bwd(ws=None, nws=0) == lib.EWORKSPACE
 
+    # the same tail with its input normalised on load
+    def tailp_fwd(ig=one, in_act=1, dt=1, ws=one, nws=1 << 40, xs=s4, xa=None, xas=None):
+        return raw.hfta_conv1x1_bn_maxpool_prenorm_fwd(8, 32, 128, 1024, 2500, dt, one, xs, ig, one, one, one, in_act, 0.0,
+                                                       one, None, one, one, 1e-5, 0.1, None, None, one, one, one, one,
+                                                       v3, one, None, 1, 0.0, xa, xas, ws, nws, None)
+    assert tailp_fwd(xa=one, xas=None) == lib.EINVAL
+    assert tailp_fwd(xa=one, xas=bad_l) == lib.EUNSUPPORTED
+    assert tailp_fwd(xa=C.c_void_p(258), xas=s4) == lib.EUNSUPPORTED          # 8-byte alignment
+    assert tailp_fwd(ig=None) == lib.EINVAL
+    assert tailp_fwd(in_act=lib.ACT_TANH) == lib.EUNSUPPORTED
+    assert tailp_fwd(dt=0) == lib.EUNSUPPORTED
+    assert tailp_fwd(xs=bad_l) == lib.EUNSUPPORTED
+    assert tailp_fwd(ws=None, nws=0) == lib.EWORKSPACE
+
+    def tailp_bwd(ig=one, in_act=1, zhit=one, ws=one, nws=1 << 40):
+        return raw.hfta_conv1x1_bn_maxpool_prenorm_bwd(8, 32, 128, 1024, 2500, 1, one, s4, ig, one, one, one, in_act, 0.0,
+                                                       one, None, zhit, None, one, one, v3, one, one, one, one, one, s4,
+                                                       one, None, one, one, 1, 0.0, ws, nws, None)
+    assert tailp_bwd(ig=None) == lib.EINVAL
+    assert tailp_bwd(zhit=None) == lib.EINVAL
+    assert tailp_bwd(in_act=lib.ACT_TANH) == lib.EUNSUPPORTED
+    assert tailp_bwd(ws=None, nws=0) == lib.EWORKSPACE
+
+    # ---- normalisation with given statistics
+    def bn_apply(B=8, mean=one, xs=s4, act=1):
+        return raw.hfta_bn_apply_fwd(B, 32, 128, 2500, 1, one, xs, one, one, mean, one, one, s4, act, 0.0, None)
+    assert bn_apply(B=0) == lib.EINVAL
+    assert bn_apply(mean=None) == lib.EINVAL
+    assert bn_apply(xs=bad_l) == lib.EUNSUPPORTED
+    assert bn_apply(act=lib.ACT_TANH) == lib.EUNSUPPORTED
+
     # ---- conv + BatchNorm as one call per direction
     assert raw.hfta_conv1x1_bn_fwd_workspace_bytes(8, 32, 64, 64, 2500, 1) == 8 * 32 * 20 * 64 * 2 * 4
     assert raw.hfta_conv1x1_bn_fwd_workspace_bytes(8, 32, 64, 64, 2500, 0) == 0               # fp32: the two operators, no workspace

@@ -1029,6 +1029,33 @@ def test_conv1x1_bn_maxpool_bwd_fused(hb, B, Nb, Ci, Co, L, act):
     assert torch.equal(dG, dG2) or np.abs(host(dG) - host(dG2)).max() <= 1e-5 * max(np.abs(rdg).max(), sc * 1e-2)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Nb,C,L,act", [(3, 5, 10, 37, 1), (2, 4, 64, 260, 2), (1, 3, 7, 1, 0), (2, 40, 16, 2500, 1)])
+def test_bn_apply_fwd(hb, B, Nb, C, L, act, dtype):
+    """Normalisation with given statistics: against the oracle's normalisation by given estimates, on
+    statistics chosen freely (not those of the input), and bit for bit what the training forward
+    stored when handed the statistics it saved."""
+    print(f"bn apply B={B} Nb={Nb} C={C} L={L} act={act} {dtype}", flush=True)
+    oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
+    x = hi.snap(hi.normal(171, (Nb, B * C, L)) * 1.3 + 0.2, dtype)
+    g = (hi.normal(172, (B * C,)) * 0.5 + 1.0).astype(np.float32)
+    bt = (hi.normal(173, (B * C,)) * 0.3).astype(np.float32)
+    mean = (hi.normal(174, (B * C,)) * 0.4).astype(np.float32)
+    invstd = (np.abs(hi.normal(175, (B * C,))) * 0.5 + 0.5).astype(np.float32)
+    var = 1.0 / invstd.astype(np.float64) ** 2                  # the oracle takes a variance and eps: eps = 0
+    ref = oops.act_fwd(oa.bn_eval_fwd(B, x, g, bt, mean, var, 0.0), oact, 0.2)
+    sx = conv_strides(B, C, L)
+    X, G, Bt, Y = dev(x, dtype), dev(g), dev(bt), empty((Nb, B * C, L), dtype)
+    hb.bn_apply_fwd(B, Nb, C, L, DT[dtype], X, sx, G, Bt, dev(mean), dev(invstd), Y, sx, act, 0.2)
+    extra = 4 * 2.0 ** -24 * np.abs(g * invstd) * (1.0 + np.abs(mean))
+    check(host(Y), ref, TOL[dtype], "y", extra[None, :, None] * (np.abs(x) + 1))
+    f32 = torch.float32
+    SM, SI, Y1, Y2 = empty((B * C,), f32), empty((B * C,), f32), empty((Nb, B * C, L), dtype), empty((Nb, B * C, L), dtype)
+    hb.bn_fwd(B, Nb, C, L, DT[dtype], X, sx, G, Bt, 1e-5, 0.1, None, None, SM, SI, Y1, sx, act, 0.2)
+    hb.bn_apply_fwd(B, Nb, C, L, DT[dtype], X, sx, G, Bt, SM, SI, Y2, sx, act, 0.2)
+    assert torch.equal(Y1, Y2)
+
+
 @pytest.mark.parametrize("B,Nb,Ci,Co,L,in_act,saved", [(2, 3, 128, 1024, 644, 1, True), (2, 4, 64, 200, 260, 2, False),
                                                         (3, 2, 24, 72, 132, 1, True)])
 def test_conv1x1_bn_maxpool_prenorm(hb, B, Nb, Ci, Co, L, in_act, saved):
@@ -1058,7 +1085,7 @@ def test_conv1x1_bn_maxpool_prenorm(hb, B, Nb, Ci, Co, L, in_act, saved):
     assert nws > 0
     ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
     out = {}
-    for kind in ("plain", "prenorm"):
+    for kind in ("plain", "prenorm", "written"):
         SM, SI = empty((B * Co,), f32), empty((B * Co,), f32)
         RM, RV = dev(np.zeros(B * Co, np.float32)), dev(np.ones(B * Co, np.float32))
         V, I = empty((B, Nb, Co), dtype), torch.empty(B, Nb, Co, dtype=torch.int32, device="cuda")
@@ -1072,6 +1099,13 @@ def test_conv1x1_bn_maxpool_prenorm(hb, B, Nb, Ci, Co, L, in_act, saved):
                                       1, 0.0, ws)
             hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], X, sx, W, Bs, None, None, ZH, SAV, dV, I, vs, G, Bt, SM, SI, dX,
                                       sx, dW, db, dG, dB, 1, 0.0, ws)
+        elif kind == "written":        # the forward's first kernel writes the activated input out; plain backward on that
+            XA = torch.full((Nb, B * Ci, L), float("nan"), dtype=TDT[dtype], device="cuda")
+            hb.conv1x1_bn_maxpool_prenorm_fwd(B, Nb, Ci, Co, L, DT[dtype], Xp, sx, Gi, Bi_, MI, II, in_act, 0.2, W, Bs, G, Bt, 1e-5,
+                                              0.1, RM, RV, SM, SI, V, I, vs, ZH, SAV, 1, 0.0, ws, Xact=XA, xas=sx)
+            assert torch.equal(XA, X), "the activated input written on the way differs from the stored one"
+            hb.conv1x1_bn_maxpool_bwd(B, Nb, Ci, Co, L, DT[dtype], XA, sx, W, Bs, None, None, ZH, SAV, dV, I, vs, G, Bt, SM, SI, dX,
+                                      sx, dW, db, dG, dB, 1, 0.0, ws)
         else:
             hb.conv1x1_bn_maxpool_prenorm_fwd(B, Nb, Ci, Co, L, DT[dtype], Xp, sx, Gi, Bi_, MI, II, in_act, 0.2, W, Bs, G, Bt, 1e-5,
                                               0.1, RM, RV, SM, SI, V, I, vs, ZH, SAV, 1, 0.0, ws)
@@ -1079,7 +1113,8 @@ def test_conv1x1_bn_maxpool_prenorm(hb, B, Nb, Ci, Co, L, in_act, saved):
                                               vs, G, Bt, SM, SI, dX, sx, dW, db, dG, dB, 1, 0.0, ws)
         out[kind] = dict(V=V, I=I, ZH=ZH, SM=SM, SI=SI, RM=RM, RV=RV, dX=dX, dW=dW, db=db, dG=dG, dB=dB)
     for k, v in out["plain"].items():
-        assert torch.equal(v, out["prenorm"][k]), f"{k} differs from the plain operator on the stored activated tensor"
+        for kind in ("prenorm", "written"):
+            assert torch.equal(v, out[kind][k]), f"{k} ({kind}) differs from the plain operator on the stored activated tensor"
     assert bool(torch.isfinite(out["prenorm"]["dX"].float()).all()) and float(out["prenorm"]["dW"].abs().max()) > 0
 
 

@@ -453,3 +453,27 @@ def test_partial_fusion_matches_full_fusion(dtype, unfused):
         for b in range(spec.B):
             tf, tp = full.param_host(full.theta, name, b), part.param_host(part.theta, name, b)
             assert np.abs(tf - tp).max() <= 2 * 2.5 * float(inp["lr"][b]), (name, b)
+
+
+def test_tail_forms_its_own_input_bit_identical():
+    """The layer in front of the one-operator tail skips its normalisation pass and the tail's first kernel
+    forms (and writes) the activated tensor from the stored pre-activation: the same bits everywhere, so
+    losses, every gradient and every updated parameter equal the default path's over two steps; and every
+    call of a step still passes its in-place check against the oracle."""
+    from paper_2102_02344_amd.arrays import FusedPointNetCls
+    spec = hi.spec_c1(B=3, Nb=4, L=500, dtype="bf16")
+    inp = hi.pointnet_cls_inputs(spec)
+    base = FusedPointNetCls(spec, inp)
+    alt = FusedPointNetCls(spec, inp, tail_prenorm=True)
+    assert alt.tail_prenorm and alt.a[alt.nconv - 2] is None and not base.tail_prenorm
+    for step in range(2):
+        base.train_step()
+        alt.train_step()
+        torch.cuda.synchronize()
+        assert torch.equal(base.loss, alt.loss), step
+        assert torch.equal(base.grad, alt.grad), step
+        assert torch.equal(base.theta, alt.theta), step
+    assert torch.equal(base.a[base.nconv - 2], alt.tail_x)
+    seen = []
+    FusedPointNetCls(spec, inp, tail_prenorm=True).forward_backward(in_place_probe(spec, seen))
+    assert "conv1x1_bn_maxpool_fwd" in seen and "conv1x1_bn_maxpool_bwd" in seen
