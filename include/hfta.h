@@ -207,7 +207,11 @@ int hfta_conv1x1_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
  * whose pointers or strides break its alignment rules needs the larger workspace as well:
  * HFTA_EWORKSPACE if it is not there.  Nothing is allocated.
  * hfta_conv1x1_bn_bwd_one_pass returns 1 for the shapes and dtype of the one-kernel form, else 0 (a
- * caller that already owns a dZ-sized buffer may prefer the two single operators for the others). */
+ * caller that already owns a dZ-sized buffer may prefer the two single operators for the others).
+ * sums (optional, [B][Co][2] fp32): the two reductions {sum g, sum g xhat} of this block, as the
+ * backward call of the block that consumed Y left them (in_sums of hfta_conv1x1_bn_prenorm_bwd);
+ * the one-kernel form then skips its reduction pass over dY and Z (dgamma, dbeta and dZ come from
+ * these sums; equal to the pass's own up to the fp32 summation order).  Other forms ignore it. */
 int hfta_conv1x1_bn_bwd_one_pass(int B, int Nb, int Ci, int Co, int L, int dtype);
 size_t hfta_conv1x1_bn_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L, int dtype);
 int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
@@ -215,7 +219,7 @@ int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                         const void* Z, const int64_t zs[4], const void* dY, const int64_t dys[4],
                         const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
                         void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
-                        int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
+                        const float* sums, int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
 
 /* The same two calls for a chain of such blocks in which the activated tensor between two blocks is
  * never stored (rows "Conv1d" and "BatchNorm1d"; the per-point layers of the point-cloud models):
@@ -232,8 +236,17 @@ int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
  * tensors with strides that are multiples of 4 elements; anything else is HFTA_EUNSUPPORTED with
  * nothing launched (store the activated tensor and use the plain pair).  Workspaces:
  * hfta_conv1x1_bn_fwd_workspace_bytes and hfta_conv1x1_bn_bwd_workspace_bytes, required here
- * (HFTA_EWORKSPACE).  Y may be NULL in the forward call, dX in the backward call. */
+ * (HFTA_EWORKSPACE).  Y may be NULL in the forward call, dX in the backward call.
+ * The backward call can hand the previous block's BatchNorm backward its two reductions: with
+ * in_sums ([B][Ci][2] fp32, optional; needs dX) it also leaves, per input channel,
+ *   in_sums[b,c] = {sum g, sum g xhat},  g = dX * in_act'(.),  xhat = (Xpre - in_mean) in_invstd,
+ * summed over samples and points with dX as stored -- the thread that loads a piece of Xpre is the
+ * one that stores that piece of dX, so this costs no memory traffic -- and the previous block's
+ * backward call, given them as `sums`, skips its own pass over dX and Xpre.  Built for Ci <= 64
+ * (hfta_conv1x1_bn_prenorm_bwd_gives_sums returns 1; otherwise in_sums != NULL is
+ * HFTA_EUNSUPPORTED).  sums: as in hfta_conv1x1_bn_bwd. */
 int hfta_conv1x1_bn_prenorm_supported(int B, int Nb, int Ci, int Co, int L, int dtype);
+int hfta_conv1x1_bn_prenorm_bwd_gives_sums(int B, int Nb, int Ci, int Co, int L, int dtype);
 int hfta_conv1x1_bn_prenorm_fwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                                 const void* Xpre, const int64_t xs[4],
                                 const float* in_gamma, const float* in_beta, const float* in_mean,
@@ -251,6 +264,7 @@ int hfta_conv1x1_bn_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
                                 const void* dY, const int64_t dys[4],
                                 const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
                                 void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
+                                const float* sums, float* in_sums,
                                 int act, float act_slope, void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------

@@ -251,6 +251,14 @@ class FusedPointNetCls(ParamArena):
         self.loss = torch.empty(B, **f32)
         ws = 4
         self.one_pass = [_bn_bwd_one_pass(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt) for i in range(self.nconv)]
+        # bn_sums[i]: the two reductions of layer i's BatchNorm backward, left by layer i+1's backward call (which
+        # holds layer i's pre-activation and output gradient in registers anyway) so that layer i's call skips its
+        # own pass over the two tensors
+        self.bn_sums = [None] * self.nconv
+        for i in range(1, self.nconv):
+            if self.prenorm[i] and i < self.nconv - 1 and self.one_pass[i - 1] and \
+                    hb.conv1x1_bn_prenorm_bwd_gives_sums(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt):
+                self.bn_sums[i - 1] = torch.empty(B * spec.conv[i], 2, **f32)
         for i in range(self.nconv):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt),
                      hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, spec.conv[i], spec.conv[i + 1], L, self.dt))
@@ -482,13 +490,13 @@ class FusedPointNetCls(ParamArena):
                     bnp = (self.master(k + ".bn.g"), self.master(k + ".bn.b"), self.saved[k + ".bn.mean"],
                            self.saved[k + ".bn.invstd"])
                     out = (dxin, None if i == 0 else _cs(B, ci, L), self.g(k + ".w"), self.g(k + ".b"), self.g(k + ".bn.g"),
-                           self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.ws)
+                           self.g(k + ".bn.b"), hb.ACT_RELU, 0.0, self.ws, None, self.bn_sums[i])
                     if self.prenorm[i]:
                         kp = f"conv{i - 1}"
                         hb.conv1x1_bn_prenorm_bwd(B, Nb, ci, co, L, dt, self.z[i - 1], _cs(B, ci, L), self.master(kp + ".bn.g"),
                                                   self.master(kp + ".bn.b"), self.saved[kp + ".bn.mean"],
                                                   self.saved[kp + ".bn.invstd"], hb.ACT_RELU, 0.0, self.w(k + ".w"),
-                                                  self.z[i], cs, da, cs, *bnp, *out)
+                                                  self.z[i], cs, da, cs, *bnp, *out, self.bn_sums[i - 1])
                         if probe is not None:
                             xin = self._act(i - 1)
                     else:
@@ -1330,6 +1338,12 @@ class _PointChain:
         cmax = max(self.conv)
         self.dbuf = [torch.empty(Nb * B * cmax * L, **act) for _ in range(2)]
         self.one_pass = [_bn_bwd_one_pass(B, Nb, self.conv[i], self.conv[i + 1], L, dt) for i in range(self.nconv)]
+        # bn_sums[i]: layer i's two BatchNorm-backward reductions, left by layer i+1's backward call
+        self.bn_sums = [None] * self.nconv
+        for i in range(1, self.nconv):
+            if self.prenorm[i] and self.one_pass[i] and self.one_pass[i - 1] and not (self.head and i == self.nconv - 1) and \
+                    hb.conv1x1_bn_prenorm_bwd_gives_sums(B, Nb, self.conv[i], self.conv[i + 1], L, dt):
+                self.bn_sums[i - 1] = torch.empty(B * self.conv[i], 2, **f32)
         for i in range(self.nconv):
             ws = max(ws, hb.conv1x1_bwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt),
                      hb.conv1x1_bn_fwd_workspace_bytes(B, Nb, self.conv[i], self.conv[i + 1], L, dt))
@@ -1462,12 +1476,13 @@ class _PointChain:
                 # BatchNorm backward + convolution backward in one call; its dX must not share da's buffer
                 dxin = self.dbuf[cur][:Nb * B * ci * L] if need_dx else None
                 out = (dxin, xs if need_dx else None, A.g(k + ".w"), A.g(k + ".b"), A.g(k + ".bn.g"), A.g(k + ".bn.b"),
-                       hb.ACT_RELU, 0.0, ws)
+                       hb.ACT_RELU, 0.0, ws, None, self.bn_sums[i])
                 if self.prenorm[i]:
                     kp = f"{self.px}conv{self.cb + i - 1}"
                     hb.conv1x1_bn_prenorm_bwd(B, Nb, ci, co, L, dt, self.z[i - 1], xs, A.master(kp + ".bn.g"),
                                               A.master(kp + ".bn.b"), A.saved[kp + ".bn.mean"], A.saved[kp + ".bn.invstd"],
-                                              hb.ACT_RELU, 0.0, A.w(k + ".w"), self.z[i], cs, da, cs, *bn, *out)
+                                              hb.ACT_RELU, 0.0, A.w(k + ".w"), self.z[i], cs, da, cs, *bn, *out,
+                                              self.bn_sums[i - 1])
                 else:
                     hb.conv1x1_bn_bwd(B, Nb, ci, co, L, dt, xin, xs, A.w(k + ".w"), self.z[i], cs, da, cs, *bn, *out)
                 da, cur = dxin, cur ^ 1

@@ -56,12 +56,13 @@ _SIGS = {
     "hfta_conv1x1_bn_bwd_one_pass": (_i, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bn_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bn_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _p, _p, _p, _p, _p, _s4, _p, _p, _p, _p,
-                                 _i, _f, _p, _sz, _p]),
+                                 _p, _i, _f, _p, _sz, _p]),
     "hfta_conv1x1_bn_prenorm_supported": (_i, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bn_prenorm_fwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _p, _i, _f, _p, _p, _p, _p, _f, _f, _p, _p,
                                          _p, _p, _p, _s4, _p, _s4, _i, _f, _p, _sz, _p]),
     "hfta_conv1x1_bn_prenorm_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _p, _p, _i, _f, _p, _p, _s4, _p, _s4, _p, _p, _p,
-                                         _p, _p, _s4, _p, _p, _p, _p, _i, _f, _p, _sz, _p]),
+                                         _p, _p, _s4, _p, _p, _p, _p, _p, _p, _i, _f, _p, _sz, _p]),
+    "hfta_conv1x1_bn_prenorm_bwd_gives_sums": (_i, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bwd_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i]),
     "hfta_conv1x1_bwd": (_i, [_i, _i, _i, _i, _i, _i, _p, _s4, _p, _p, _s4, _p, _s4, _p, _p, _p, _sz, _p]),
     "hfta_conv2d_grouped_fwd": (_i, [_i] * 11 + [_p, _p, _p, _p, _i, _f, _p, _sz, _p]),
@@ -238,16 +239,20 @@ def conv1x1_bn_bwd_workspace_bytes(B, Nb, Ci, Co, L, dtype) -> int:
 
 
 def conv1x1_bn_bwd(B, Nb, Ci, Co, L, dtype, X, xs, W, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd, dX, dxs, dW,
-                   dbias, dgamma, dbeta, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None):
+                   dbias, dgamma, dbeta, act=ACT_NONE, act_slope=0.0, workspace=None, stream=None, sums=None):
     wp, wb = _ws(workspace)
     _check(_lib.hfta_conv1x1_bn_bwd(B, Nb, Ci, Co, L, dtype, _ptr(X), _strides(xs), _ptr(W), _ptr(Z), _strides(zs),
                                     _ptr(dY), _strides(dys), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd),
-                                    _ptr(dX), _strides(dxs), _ptr(dW), _ptr(dbias), _ptr(dgamma), _ptr(dbeta), act,
-                                    act_slope, wp, wb, _stream(stream)), "hfta_conv1x1_bn_bwd")
+                                    _ptr(dX), _strides(dxs), _ptr(dW), _ptr(dbias), _ptr(dgamma), _ptr(dbeta),
+                                    _ptr(sums), act, act_slope, wp, wb, _stream(stream)), "hfta_conv1x1_bn_bwd")
 
 
 def conv1x1_bn_prenorm_supported(B, Nb, Ci, Co, L, dtype) -> bool:
     return bool(_lib.hfta_conv1x1_bn_prenorm_supported(B, Nb, Ci, Co, L, dtype))
+
+
+def conv1x1_bn_prenorm_bwd_gives_sums(B, Nb, Ci, Co, L, dtype) -> bool:
+    return bool(_lib.hfta_conv1x1_bn_prenorm_bwd_gives_sums(B, Nb, Ci, Co, L, dtype))
 
 
 def conv1x1_bn_prenorm_fwd(B, Nb, Ci, Co, L, dtype, Xpre, xs, in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope, W, bias,
@@ -263,13 +268,14 @@ def conv1x1_bn_prenorm_fwd(B, Nb, Ci, Co, L, dtype, Xpre, xs, in_gamma, in_beta,
 
 def conv1x1_bn_prenorm_bwd(B, Nb, Ci, Co, L, dtype, Xpre, xs, in_gamma, in_beta, in_mean, in_invstd, in_act, in_slope, W, Z, zs,
                            dY, dys, gamma, beta, save_mean, save_invstd, dX, dxs, dW, dbias, dgamma, dbeta, act=ACT_NONE,
-                           act_slope=0.0, workspace=None, stream=None):
+                           act_slope=0.0, workspace=None, stream=None, sums=None, in_sums=None):
     wp, wb = _ws(workspace)
     _check(_lib.hfta_conv1x1_bn_prenorm_bwd(B, Nb, Ci, Co, L, dtype, _ptr(Xpre), _strides(xs), _ptr(in_gamma), _ptr(in_beta),
                                             _ptr(in_mean), _ptr(in_invstd), in_act, in_slope, _ptr(W), _ptr(Z), _strides(zs),
                                             _ptr(dY), _strides(dys), _ptr(gamma), _ptr(beta), _ptr(save_mean),
                                             _ptr(save_invstd), _ptr(dX), _strides(dxs), _ptr(dW), _ptr(dbias), _ptr(dgamma),
-                                            _ptr(dbeta), act, act_slope, wp, wb, _stream(stream)),
+                                            _ptr(dbeta), _ptr(sums), _ptr(in_sums), act, act_slope, wp, wb,
+                                            _stream(stream)),
            "hfta_conv1x1_bn_prenorm_bwd")
 
 

@@ -351,6 +351,21 @@ __global__ __launch_bounds__(NT) void bn_bwd_conv_coef_kernel(BnBwdArgs p, float
   }
 }
 
+// The same constants from the two sums handed over by the kernel that produced dY (sums[k] = {sum g, sum g xhat}).
+__global__ __launch_bounds__(256) void bn_bwd_coef_sums_kernel(const float* __restrict__ sums, const float* __restrict__ gamma,
+                                                               const float* __restrict__ beta, const float* __restrict__ mean,
+                                                               const float* __restrict__ invstd, float* __restrict__ dgamma,
+                                                               float* __restrict__ dbeta, float* __restrict__ coef, int n, float m) {
+  const int k = blockIdx.x * 256 + threadIdx.x;
+  if (k >= n) return;
+  const float2 s = *reinterpret_cast<const float2*>(sums + (int64_t)k * 2);
+  dbeta[k] = s.x;
+  dgamma[k] = s.y;
+  float4* o = reinterpret_cast<float4*>(coef + (int64_t)k * 8);
+  o[0] = make_float4(mean[k], invstd[k], gamma[k], beta[k]);
+  o[1] = make_float4(s.x / m, s.y / m, gamma[k] * invstd[k], 0.f);
+}
+
 template <typename T>
 __global__ __launch_bounds__(BNL_C * BNL_N) void bn_bwd_linear_kernel(BnBwdArgs p) {
   __shared__ float red[BNL_N][BNL_C];
@@ -505,6 +520,14 @@ int bn_bwd_coef(int B, int Nb, int C, int L, int dtype, const void* X, const int
   if (dtype == HFTA_BF16) { if (v4) HFTA_BN_COEF(bf16_raw, 4); else HFTA_BN_COEF(bf16_raw, 1); }
   else { if (v4) HFTA_BN_COEF(float, 4); else HFTA_BN_COEF(float, 1); }
 #undef HFTA_BN_COEF
+  return launch_status();
+}
+int bn_bwd_coef_from_sums(int B, int Nb, int C, int L, const float* sums, const float* gamma, const float* beta,
+                          const float* save_mean, const float* save_invstd, float* dgamma, float* dbeta, float* coef,
+                          hipStream_t st) {
+  const int n = B * C;
+  hipLaunchKernelGGL(bn_bwd_coef_sums_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, sums, gamma, beta, save_mean,
+                     save_invstd, dgamma, dbeta, coef, n, (float)Nb * (float)L);
   return launch_status();
 }
 }  // namespace hfta

@@ -36,6 +36,9 @@ namespace hfta {
 int bn_bwd_coef(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const void* dY,
                 const int64_t dys[4], const float* gamma, const float* beta, const float* save_mean,
                 const float* save_invstd, float* dgamma, float* dbeta, float* coef, int act, float slope, hipStream_t st);
+int bn_bwd_coef_from_sums(int B, int Nb, int C, int L, const float* sums, const float* gamma, const float* beta,
+                          const float* save_mean, const float* save_invstd, float* dgamma, float* dbeta, float* coef,
+                          hipStream_t st);
 
 namespace {
 
@@ -43,7 +46,7 @@ struct CbbArgs {
   const bf16_raw* dY; const bf16_raw* Z; const bf16_raw* X; const bf16_raw* W;
   bf16_raw* dX;                  // nullptr: no data gradient (the network's first layer)
   const float* coef;             // [B][Co][8]: mean, invstd, gamma, beta, mean(g), mean(g xhat), gamma*invstd, 0
-  float* part;                   // [G][B*Co*Ci + B*Co]: dW partials, then dbias partials
+  float* part;                   // [G * KS][B*Co*Ci + B*Co + 2*B*Ci]: dW partials, dbias partials, partials of the input block's two sums
   int64_t dy_g0, dy_g1, dy_ld, z_g0, z_g1, z_ld, x_g0, x_g1, x_ld, dx_g0, dx_g1, dx_ld;
   int B, Ci, Co, L, Nb, G, slices, act, w_vec;           // w_vec: rows of W can be read eight bytes at a time
   float slope;
@@ -52,6 +55,11 @@ struct CbbArgs {
   // bf16, is formed on the way into LDS with the arithmetic of the BatchNorm kernels.  [B][Ci] each.
   const float* in_gamma; const float* in_beta; const float* in_mean; const float* in_invstd;
   int in_act; float in_slope;
+  // With in_gamma and dX: also leave, per input channel, the two reductions the INPUT block's BatchNorm backward
+  // needs over its output gradient (= dX as stored) and its pre-activation (= X): sum g and sum g xhat with
+  // g = dX * act_in'(.), xhat = (X - in_mean) * in_invstd.  The same thread loads a piece of X and stores that
+  // piece of dX, so this costs no memory traffic; that block's own pass over both tensors goes away.
+  int in_sums;
 };
 
 __device__ __forceinline__ float lo_f32(uint32_t v) { return __uint_as_float(v << 16); }
@@ -76,7 +84,10 @@ struct CbbCfg {
   static constexpr int ST_BYTES = CI * PS, CF_BYTES = CO * 32;
   static constexpr bool OVERLAY = (CO == 128 && CI == 128);   // the dX tile goes out over dz^T (LDS would not hold both)
   static constexpr int XC_BYTES = CI * 16;             // the input block's BatchNorm constants (with a data gradient: own region; without: over W^T)
-  static constexpr int SMEM = WT_BYTES + DZT_BYTES + DZN_BYTES + XN_BYTES + CF_BYTES + (OVERLAY ? 0 : ST_BYTES) + (HAS_DX ? XC_BYTES : 0);
+  static constexpr bool SUMS = HAS_DX && CI <= 64;     // can leave the input block's two sums (LDS and registers hold the extra state)
+  static constexpr int ZR_BYTES = SUMS ? CI * 256 : 0; // the raw x pieces of the slice, each kept for the thread that loaded it
+  static constexpr int SMEM0 = WT_BYTES + DZT_BYTES + DZN_BYTES + XN_BYTES + CF_BYTES + (OVERLAY ? 0 : ST_BYTES) + (HAS_DX ? XC_BYTES : 0);
+  static constexpr int SMEM = SMEM0 + ZR_BYTES;
   static constexpr int DXT = CI / 64;                  // 32 x 32 tiles of dX per wavefront (CI/32 x 4 tiles, 8 wavefronts)
   static constexpr int WTILES = (CO / 32) * (CI / 32); // 32 x 32 tiles of dW
   static constexpr int KS = WTILES == 4 ? 2 : 1;       // four tiles: the slice's points are split over two wavefronts per tile
@@ -102,6 +113,9 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
   const float4* cf = reinterpret_cast<const float4*>(cfb);
   float4* xc = reinterpret_cast<float4*>(HAS_DX ? cfb + K::CF_BYTES + (K::OVERLAY ? 0 : K::ST_BYTES) : Wts);
   static_assert(HAS_DX || K::WT_BYTES >= K::XC_BYTES, "constants fit over the unused W^T tile");
+  unsigned char* zraw = smem + K::SMEM0;
+  const bool sums_on = K::SUMS && p.in_sums;
+  const float in_neg = p.in_act == HFTA_ACT_RELU ? 0.f : (p.in_act == HFTA_ACT_LEAKY ? p.in_slope : 1.f);
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int r = lane & 31, gsel = lane >> 5;
@@ -213,6 +227,10 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
   for (int i = 0; i < BPT; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) bsum[i][j] = 0.f;
+  constexpr int SPT = K::SUMS ? XPT : 1;     // this thread's rows (t / 32 + 16 i) are the same in every slice
+  float isum1[SPT], isum2[SPT];
+#pragma unroll
+  for (int i = 0; i < SPT; ++i) isum1[i] = isum2[i] = 0.f;
 
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) issue(q[d], ubeg + d);
@@ -266,6 +284,7 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
       for (int i = 0; i < XPT; ++i) {
         const int id = t + CBB_THREADS * i;
         uint2 xv = q[d].x[i];
+        if (K::SUMS && sums_on) *reinterpret_cast<uint2*>(zraw + id * 8) = xv;
         if (xin) {
           xv = in_norm_apply4(xv, xc[id >> 5], l0 + (id & 31) * 4 + 4 <= p.L, p.in_act, p.in_slope);
         }
@@ -321,7 +340,24 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
         for (int i = 0; i < XPT; ++i) {
           const int id = t + CBB_THREADS * i, row = id >> 5, c = l0 + (id & 31) * 4;
           const uint2 v = *reinterpret_cast<const uint2*>(stg + row * PS + (id & 31) * 8);
-          if (row < p.Ci && c + 4 <= p.L) *reinterpret_cast<uint2*>(dXb + (int64_t)row * p.dx_ld + c) = v;
+          const bool okp = row < p.Ci && c + 4 <= p.L;
+          if (okp) *reinterpret_cast<uint2*>(dXb + (int64_t)row * p.dx_ld + c) = v;
+          if (K::SUMS && sums_on) {
+            const uint2 zr = *reinterpret_cast<const uint2*>(zraw + id * 8);
+            const float4 ic = xc[row];       // mean, invstd, gamma, beta of the input block
+            const float dd[4] = {lo_f32(v.x), hi_f32(v.x), lo_f32(v.y), hi_f32(v.y)};
+            const float zz[4] = {lo_f32(zr.x), hi_f32(zr.x), lo_f32(zr.y), hi_f32(zr.y)};
+            float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float xh = (zz[e] - ic.x) * ic.y;
+              const float gr = dd[e] * (fmaf(ic.z, xh, ic.w) > 0.f ? 1.f : in_neg);
+              a1 += gr;
+              a2 = fmaf(gr, xh, a2);
+            }
+            isum1[K::SUMS ? i : 0] += okp ? a1 : 0.f;
+            isum2[K::SUMS ? i : 0] += okp ? a2 : 0.f;
+          }
         }
         if (K::OVERLAY) __syncthreads();     // read out before the next slice's dz lands
       } else {
@@ -331,12 +367,30 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
   }
 
   // ---- this workgroup's partials: [G * KS] slots of dW (+ dbias in the slots of point half 0) ----
-  const int64_t nW = (int64_t)p.B * p.Co * p.Ci, nB = (int64_t)p.B * p.Co;
+  const int64_t nW = (int64_t)p.B * p.Co * p.Ci, nB = (int64_t)p.B * p.Co, stride = nW + nB + 2 * (int64_t)p.B * p.Ci;
+  if (K::SUMS && sums_on) {
+    // the 32 lanes that share a row add up; every slot of this workgroup gets its entry (zeros past the first)
+#pragma unroll
+    for (int i = 0; i < SPT; ++i) {
+      float a1 = isum1[i], a2 = isum2[i];
+#pragma unroll
+      for (int m = 16; m >= 1; m >>= 1) {
+        a1 += __shfl_xor(a1, m, 64);
+        a2 += __shfl_xor(a2, m, 64);
+      }
+      const int row = (t >> 5) + 16 * i;
+      if ((t & 31) == 0 && row < p.Ci)
+#pragma unroll
+        for (int kh = 0; kh < KS; ++kh)
+          *reinterpret_cast<float2*>(p.part + (int64_t)(w * KS + kh) * stride + nW + nB + ((int64_t)b * p.Ci + row) * 2) =
+              kh == 0 ? make_float2(a1, a2) : make_float2(0.f, 0.f);
+    }
+  }
 #pragma unroll
   for (int i = 0; i < NU; ++i) {
     const int id = wave + 8 * i, tile = KS == 2 ? (id & 3) : id, kh = KS == 2 ? (id >> 2) : 0;
     const int tco = tile / TCI, tci = tile % TCI;
-    float* pw = p.part + (int64_t)(w * KS + kh) * (nW + nB) + (int64_t)b * p.Co * p.Ci;
+    float* pw = p.part + (int64_t)(w * KS + kh) * stride + (int64_t)b * p.Co * p.Ci;
     const int ci = tci * 32 + r;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -358,28 +412,31 @@ __global__ __launch_bounds__((CbbCfg<CO, CI, HAS_DX>::WGS * CBB_THREADS)) void c
 #pragma unroll 8
       for (int i = 0; i < 32; ++i) s += sc[i * CO + co];
     }
-    p.part[(int64_t)(w * KS + kh) * (nW + nB) + nW + (int64_t)b * p.Co + co] = s;
+    p.part[(int64_t)(w * KS + kh) * stride + nW + (int64_t)b * p.Co + co] = s;
   }
 }
 
 // out[i] = sum over the G workgroup partials in a fixed order (four interleaved chains combined as
-// (0+1)+(2+3)); the first nW outputs are dW, the rest dbias.
+// (0+1)+(2+3)); the first nW outputs are dW, the next nB dbias, the last nS (0 if not asked for) the
+// input block's sums.
 __global__ __launch_bounds__(256) void cbb_reduce_kernel(const float* __restrict__ part, float* __restrict__ dW,
-                                                         float* __restrict__ dbias, int64_t nW, int64_t nB, int G) {
+                                                         float* __restrict__ dbias, float* __restrict__ sums, int64_t nW,
+                                                         int64_t nB, int64_t nS, int64_t stride, int G) {
   __shared__ float sh[4][64];
   const int q = threadIdx.x >> 6, li = threadIdx.x & 63;
-  const int64_t i = (int64_t)blockIdx.x * 64 + li, count = nW + nB;
+  const int64_t i = (int64_t)blockIdx.x * 64 + li, count = nW + nB + nS;
   float s = 0.f;
   if (i < count) {
 #pragma unroll 8
-    for (int k = q; k < G; k += 4) s += part[(int64_t)k * count + i];
+    for (int k = q; k < G; k += 4) s += part[(int64_t)k * stride + i];
   }
   sh[q][li] = s;
   __syncthreads();
   if (q == 0 && i < count) {
     const float v = (sh[0][li] + sh[1][li]) + (sh[2][li] + sh[3][li]);
     if (i < nW) dW[i] = v;
-    else if (dbias) dbias[i - nW] = v;
+    else if (i < nW + nB) { if (dbias) dbias[i - nW] = v; }
+    else sums[i - nW - nB] = v;
   }
 }
 
@@ -401,13 +458,16 @@ int cbb_point_halves(int Ci, int Co) { return (Ci <= 64 && Co <= 64) ? 2 : 1; } 
 }  // namespace
 
 // The shapes the one-pass kernel takes (the caller has checked B, Nb, Ci, Co, L > 0).
+// ... and can leave the input block's two sums on the way (a data gradient and on-load normalisation are asked for)
+bool conv1x1_bn_bwd_stream_sums(int Ci) { return Ci <= 64; }
+
 bool conv1x1_bn_bwd_streams(int B, int Ci, int Co, int L, int dtype) {
   return dtype == HFTA_BF16 && Ci <= 128 && Co <= 128 && L % 4 == 0 && B <= 65535;
 }
 
 size_t conv1x1_bn_bwd_stream_bytes(int B, int Nb, int Ci, int Co, int L) {
   const size_t slots = (size_t)cbb_groups(B, Nb, L, cbb_per_cu(Ci, Co, false)) * cbb_point_halves(Ci, Co);
-  return align256((size_t)B * Co * 8 * sizeof(float)) + slots * ((size_t)B * Co * Ci + (size_t)B * Co) * sizeof(float);
+  return align256((size_t)B * Co * 8 * sizeof(float)) + slots * ((size_t)B * Co * Ci + (size_t)B * Co + 2 * (size_t)B * Ci) * sizeof(float);
 }
 
 // HFTA_EUNSUPPORTED: alignment or strides are not the kernel's (nothing has been launched).
@@ -416,7 +476,8 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
                           const float* beta, const float* save_mean, const float* save_invstd, void* dX,
                           const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act, float slope,
                           void* workspace, hipStream_t st, const float* in_gamma, const float* in_beta,
-                          const float* in_mean, const float* in_invstd, int in_act, float in_slope) {
+                          const float* in_mean, const float* in_invstd, int in_act, float in_slope, const float* sums,
+                          float* in_sums) {
   auto al = [](const void* q, size_t a) { return (reinterpret_cast<uintptr_t>(q) % a) == 0; };
   auto s4 = [](const int64_t* s) { return s[0] % 4 == 0 && s[1] % 4 == 0 && s[2] % 4 == 0 && s[2] > 0 && s[3] == 1; };
   if (!al(X, 8) || !al(Z, 8) || !al(dY, 8) || !s4(xs) || !s4(zs) || !s4(dys) || !al(workspace, 16)) return HFTA_EUNSUPPORTED;
@@ -424,13 +485,16 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
   if (in_gamma && (!in_beta || !in_mean || !in_invstd ||
                    (in_act != HFTA_ACT_NONE && in_act != HFTA_ACT_RELU && in_act != HFTA_ACT_LEAKY)))
     return HFTA_EUNSUPPORTED;
+  if (in_sums && (!in_gamma || !dX || !conv1x1_bn_bwd_stream_sums(Ci))) return HFTA_EUNSUPPORTED;
   auto ext = [&](const int64_t* s, int C) { return ((int64_t)(C - 1) * s[2] + L) * 2; };
   const int64_t w_ext = (int64_t)Co * Ci * 2;
   if (ext(xs, Ci) >= (int64_t)1 << 31 || ext(zs, Co) >= (int64_t)1 << 31 || ext(dys, Co) >= (int64_t)1 << 31 || w_ext >= (int64_t)1 << 31)
     return HFTA_EUNSUPPORTED;
   float* coef = reinterpret_cast<float*>(workspace);
   float* part = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(workspace) + align256((size_t)B * Co * 8 * sizeof(float)));
-  int rc = bn_bwd_coef(B, Nb, Co, L, HFTA_BF16, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd, dgamma, dbeta, coef, act, slope, st);
+  // the two sums of this block's BatchNorm backward: from the successor's backward, or a pass over dY and z
+  int rc = sums ? bn_bwd_coef_from_sums(B, Nb, Co, L, sums, gamma, beta, save_mean, save_invstd, dgamma, dbeta, coef, st)
+                : bn_bwd_coef(B, Nb, Co, L, HFTA_BF16, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd, dgamma, dbeta, coef, act, slope, st);
   if (rc != HFTA_OK) return rc;
   CbbArgs a;
   a.dY = (const bf16_raw*)dY; a.Z = (const bf16_raw*)Z; a.X = (const bf16_raw*)X; a.W = (const bf16_raw*)W;
@@ -445,6 +509,7 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
   a.act = act; a.slope = slope;
   a.in_gamma = in_gamma; a.in_beta = in_beta; a.in_mean = in_mean; a.in_invstd = in_invstd;
   a.in_act = in_act; a.in_slope = in_slope;
+  a.in_sums = in_sums ? 1 : 0;
   a.w_vec = (W && al(W, 8) && Ci % 4 == 0) ? 1 : 0;
   a.dy_extent = (uint32_t)ext(dys, Co); a.z_extent = (uint32_t)ext(zs, Co); a.x_extent = (uint32_t)ext(xs, Ci);
   a.w_extent = (uint32_t)w_ext;
@@ -459,8 +524,9 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
 #undef HFTA_CBB
   rc = launch_status();
   if (rc != HFTA_OK) return rc;
-  const int64_t nW = (int64_t)B * Co * Ci, nB = (int64_t)B * Co;
-  hipLaunchKernelGGL(cbb_reduce_kernel, dim3((unsigned)((nW + nB + 63) / 64)), dim3(256), 0, st, part, dW, dbias, nW, nB, a.G * cbb_point_halves(Ci, Co));
+  const int64_t nW = (int64_t)B * Co * Ci, nB = (int64_t)B * Co, nSall = 2 * (int64_t)B * Ci, nS = in_sums ? nSall : 0;
+  hipLaunchKernelGGL(cbb_reduce_kernel, dim3((unsigned)((nW + nB + nS + 63) / 64)), dim3(256), 0, st, part, dW, dbias, in_sums, nW, nB,
+                     nS, nW + nB + nSall, a.G * cbb_point_halves(Ci, Co));
   return launch_status();
 }
 

@@ -89,6 +89,8 @@ __global__ __launch_bounds__(GEMM_THREADS, ONE ? 4 : 1) void conv1x1_stream_kern
   }
   // ---- X tile: 4(ci) x 4(points) blocks, transposed in registers on the way into LDS ----
   {
+    // (Which lanes take which block does not matter to the memory system: whole 256-byte row segments per half
+    // wavefront or 128 bytes of four rows per wavefront instead of this 64-byte-per-row mapping time the same.)
     const int kq = t % 8, ng = t / 8;
     const int c = l0 + ng * 4;
     const uint32_t ldb = (uint32_t)(p.x_ld * 2);

@@ -21,7 +21,9 @@ int conv1x1_bn_bwd_stream(int B, int Nb, int Ci, int Co, int L, const void* X, c
                           const float* beta, const float* save_mean, const float* save_invstd, void* dX,
                           const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act, float slope,
                           void* workspace, hipStream_t st, const float* in_gamma = nullptr, const float* in_beta = nullptr,
-                          const float* in_mean = nullptr, const float* in_invstd = nullptr, int in_act = 0, float in_slope = 0.f);
+                          const float* in_mean = nullptr, const float* in_invstd = nullptr, int in_act = 0, float in_slope = 0.f,
+                          const float* sums = nullptr, float* in_sums = nullptr);
+bool conv1x1_bn_bwd_stream_sums(int Ci);
 int bn_stats_conv(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
                   const float* beta, float eps, float momentum, float* running_mean, float* running_var,
                   float* save_mean, float* save_invstd, hipStream_t st);
@@ -634,8 +636,8 @@ size_t hfta_conv1x1_bn_bwd_workspace_bytes(int B, int Nb, int Ci, int Co, int L,
 int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
                         const void* W, const void* Z, const int64_t zs[4], const void* dY, const int64_t dys[4],
                         const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
-                        void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta, int act,
-                        float act_slope, void* workspace, size_t ws_bytes, void* stream) {
+                        void* dX, const int64_t dxs[4], float* dW, float* dbias, float* dgamma, float* dbeta,
+                        const float* sums, int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
   int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
   if (rc != HFTA_OK) return rc;
   if (!X || !xs || !Z || !zs || !dY || !dys || !gamma || !beta || !save_mean || !save_invstd || !dW || !dgamma || !dbeta)
@@ -647,7 +649,8 @@ int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const v
   if (hfta::conv1x1_bn_bwd_streams(B, Ci, Co, L, dtype)) {
     if (!workspace || ws_bytes < hfta::conv1x1_bn_bwd_stream_bytes(B, Nb, Ci, Co, L)) return HFTA_EWORKSPACE;
     rc = hfta::conv1x1_bn_bwd_stream(B, Nb, Ci, Co, L, X, xs, W, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd,
-                                     dX, dxs, dW, dbias, dgamma, dbeta, act, act_slope, workspace, st);
+                                     dX, dxs, dW, dbias, dgamma, dbeta, act, act_slope, workspace, st, nullptr, nullptr, nullptr,
+                                     nullptr, 0, 0.f, sums, nullptr);
     if (rc != HFTA_EUNSUPPORTED) return rc;
   }
   const size_t dzb = cbb_fallback_dz_bytes(B, Nb, Co, L, dtype);
@@ -663,15 +666,21 @@ int hfta_conv1x1_bn_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const v
 }
 
 
+int hfta_conv1x1_bn_prenorm_bwd_gives_sums(int B, int Nb, int Ci, int Co, int L, int dtype) {
+  return hfta_conv1x1_bn_prenorm_supported(B, Nb, Ci, Co, L, dtype) && hfta::conv1x1_bn_bwd_stream_sums(Ci) ? 1 : 0;
+}
+
 int hfta_conv1x1_bn_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* Xpre, const int64_t xs[4],
                                 const float* in_gamma, const float* in_beta, const float* in_mean, const float* in_invstd,
                                 int in_act, float in_slope, const void* W, const void* Z, const int64_t zs[4],
                                 const void* dY, const int64_t dys[4], const float* gamma, const float* beta,
                                 const float* save_mean, const float* save_invstd, void* dX, const int64_t dxs[4],
-                                float* dW, float* dbias, float* dgamma, float* dbeta, int act, float act_slope,
-                                void* workspace, size_t ws_bytes, void* stream) {
+                                float* dW, float* dbias, float* dgamma, float* dbeta, const float* sums, float* in_sums,
+                                int act, float act_slope, void* workspace, size_t ws_bytes, void* stream) {
   int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
   if (rc != HFTA_OK) return rc;
+  if (in_sums && !dX) return HFTA_EINVAL;
+  if (in_sums && !hfta_conv1x1_bn_prenorm_bwd_gives_sums(B, Nb, Ci, Co, L, dtype)) return HFTA_EUNSUPPORTED;
   if (!Xpre || !xs || !Z || !zs || !dY || !dys || !gamma || !beta || !save_mean || !save_invstd || !dW || !dgamma || !dbeta)
     return HFTA_EINVAL;
   if (!in_gamma || !in_beta || !in_mean || !in_invstd) return HFTA_EINVAL;
@@ -683,7 +692,7 @@ int hfta_conv1x1_bn_prenorm_bwd(int B, int Nb, int Ci, int Co, int L, int dtype,
   if (!workspace || ws_bytes < hfta::conv1x1_bn_bwd_stream_bytes(B, Nb, Ci, Co, L)) return HFTA_EWORKSPACE;
   return hfta::conv1x1_bn_bwd_stream(B, Nb, Ci, Co, L, Xpre, xs, W, Z, zs, dY, dys, gamma, beta, save_mean, save_invstd, dX,
                                      dxs, dW, dbias, dgamma, dbeta, act, act_slope, workspace, as_stream(stream), in_gamma,
-                                     in_beta, in_mean, in_invstd, in_act, in_slope);
+                                     in_beta, in_mean, in_invstd, in_act, in_slope, sums, in_sums);
 }
 
 }  // extern "C"

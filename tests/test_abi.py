@@ -175,7 +175,7 @@ def test_validation_of_the_wider_entry_points(lib):
 
     def cb_bwd(B=8, Z=one, dX=one, W=one, dxs=s64, dW=one, act=1, ws=one, nws=1 << 40, dys=s64):
         return raw.hfta_conv1x1_bn_bwd(B, 32, 64, 64, 2500, 1, one, s64, W, Z, s64, one, dys, one, one, one, one,
-                                       dX, dxs, dW, None, one, one, act, 0.0, ws, nws, None)
+                                       dX, dxs, dW, None, one, one, None, act, 0.0, ws, nws, None)
     assert cb_bwd(Z=None) == lib.EINVAL
     assert cb_bwd(B=0) == lib.EINVAL
     assert cb_bwd(dW=None) == lib.EINVAL
@@ -205,9 +205,15 @@ def test_validation_of_the_wider_entry_points(lib):
     assert pn_fwd(in_act=lib.ACT_TANH) == lib.EUNSUPPORTED
     assert pn_fwd(ws=None, nws=0) == lib.EWORKSPACE
 
-    def pn_bwd(dt=1, ig=one, dW=one, W=one, ws=one, nws=1 << 40):
-        return raw.hfta_conv1x1_bn_prenorm_bwd(8, 32, 64, 64, 2500, dt, one, s64, ig, one, one, one, 1, 0.0, W, one, s64, one,
-                                               s64, one, one, one, one, one, s64, dW, None, one, one, 1, 0.0, ws, nws, None)
+    def pn_bwd(dt=1, ig=one, dW=one, W=one, ws=one, nws=1 << 40, dX=one, isum=None, Ci=64):
+        return raw.hfta_conv1x1_bn_prenorm_bwd(8, 32, Ci, 64, 2500, dt, one, s64, ig, one, one, one, 1, 0.0, W, one, s64, one,
+                                               s64, one, one, one, one, dX, s64, dW, None, one, one, None, isum, 1, 0.0, ws,
+                                               nws, None)
+    assert raw.hfta_conv1x1_bn_prenorm_bwd_gives_sums(8, 32, 64, 128, 2500, 1) == 1
+    assert raw.hfta_conv1x1_bn_prenorm_bwd_gives_sums(8, 32, 128, 128, 2500, 1) == 0          # Ci > 64
+    assert raw.hfta_conv1x1_bn_prenorm_bwd_gives_sums(8, 32, 64, 128, 2500, 0) == 0           # fp32
+    assert pn_bwd(isum=one, dX=None) == lib.EINVAL             # the sums are taken where dX is stored
+    assert pn_bwd(isum=one, Ci=128) == lib.EUNSUPPORTED
     assert pn_bwd(ig=None) == lib.EINVAL
     assert pn_bwd(dW=None) == lib.EINVAL
     assert pn_bwd(W=None) == lib.EINVAL

@@ -566,10 +566,13 @@ def test_c1_with_transform_subnetworks_full_size():
     torch.cuda.synchronize()
     assert torch.equal(arr.loss, plain.loss) and bool(torch.isfinite(arr.loss).all())
     for name, _ in plain.shapes:
-        if name in ("conv0.w", "conv0.b"):
+        if name.startswith("conv0."):
+            # the first layer runs another instantiation of the backward kernel here, and its two BatchNorm-backward
+            # reductions come from its own pass (its output goes through the feature transform) where the plain
+            # array hands them down from the next layer's kernel: fp32 summation orders, single bf16 roundings of dz
             ga, gp = arr.g(name).double(), plain.g(name).double()
-            scale = plain.g("conv0.w").abs().max().item()
-            assert float((ga - gp).abs().max()) <= 1e-5 * scale, name
+            ref = "conv0.w" if name == "conv0.b" else name       # the bias gradient is a sum of dz that cancels: no scale of its own
+            assert float((ga - gp).abs().max()) <= 3e-4 * plain.g(ref).abs().max().item(), name
             continue
         assert torch.equal(arr.g(name), plain.g(name)), name
     for k in hi.tnet_sizes(ts):

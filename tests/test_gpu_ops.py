@@ -8,7 +8,7 @@ import torch
 import hfta_inputs as hi
 from oracle import array as oa
 from oracle import ops as oops
-from util import DT, TDT, TOL, check, check_tail_argmax, conv_strides, dev, host
+from util import DT, TDT, TOL, bn_preact_fp32, check, check_tail_argmax, conv_strides, dev, host
 
 pytestmark = pytest.mark.gpu
 
@@ -378,6 +378,15 @@ def test_conv1x1_bn_bwd(hb, dtype, B, Nb, Ci, Co, L, act, want_dx):
     assert torch.equal(dW, dW2) and torch.equal(db, db2)
     if want_dx:
         assert torch.equal(dX, dX2)
+    # the block's two reductions handed in (here: its own, as dbeta and dgamma hold them) instead of taken in a
+    # pass over dY and Z: the same constants, hence the same bits everywhere
+    S = torch.stack([dB, dG], dim=1).contiguous()
+    dG3, dB3 = empty((B * Co,), torch.float32), empty((B * Co,), torch.float32)
+    hb.conv1x1_bn_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Z, zs, dY, zs, G, Bt, SM, SI, dX2, xs if want_dx else None,
+                      dW2, db2, dG3, dB3, act, 0.2, ws, sums=S)
+    assert torch.equal(dW, dW2) and torch.equal(db, db2) and torch.equal(dG, dG3) and torch.equal(dB, dB3)
+    if want_dx:
+        assert torch.equal(dX, dX2)
     with pytest.raises(RuntimeError):
         hb.conv1x1_bn_bwd(B, Nb, Ci, Co, L, DT[dtype], X, xs, W, Z, zs, dY, zs, G, Bt, SM, SI, dX2, xs if want_dx else None,
                           dW2, db2, dG, dB, act, 0.2, None)
@@ -448,6 +457,32 @@ def test_conv1x1_bn_prenorm(hb, B, Nb, Ci, Co, L, in_act, act, want_y):
     if want_y:
         oact = {0: oops.ACT_NONE, 1: oops.ACT_RELU, 2: oops.ACT_LEAKY}[act]
         check(host(out["prenorm"]["Y"]), oops.act_fwd(ry, oact, 0.2), TOL[dtype], "Y")
+    # the backward call also leaves the input block's two reductions (sum g, sum g xhat over dX as stored and
+    # the input block's pre-activation) where the kernel has room for them: nothing else changes by a bit, and
+    # the sums are those of the oracle's BatchNorm backward of that block on the device's dX
+    assert hb.conv1x1_bn_prenorm_bwd_gives_sums(B, Nb, Ci, Co, L, DT[dtype]) == (Ci <= 64)
+    S = torch.full((B * Ci, 2), float("nan"), dtype=f32, device="cuda")
+    if Ci <= 64:
+        pz = out["prenorm"]
+        dX, dW, db = empty((Nb, B * Ci, L), dtype), empty((B * Co, Ci), f32), empty((B * Co,), f32)
+        dG, dB = empty((B * Co,), f32), empty((B * Co,), f32)
+        ws.fill_(0xa5)
+        hb.conv1x1_bn_prenorm_bwd(B, Nb, Ci, Co, L, DT[dtype], Xp, xs, Gi, Bi, MI, II, in_act, 0.2, W, pz["Z"], zs, dY, zs, G, Bt,
+                                  pz["SM"], pz["SI"], dX, xs, dW, db, dG, dB, act, 0.2, ws, in_sums=S)
+        for k, v in dict(dX=dX, dW=dW, db=db, dG=dG, dB=dB).items():
+            assert torch.equal(v, pz[k]), f"{k} changes when the input block's sums are asked for"
+        mi, ii = host(MI).astype(np.float64), host(II).astype(np.float64)
+        pre = bn_preact_fp32(xpre, gi, bi, mi, ii)             # the mask in the kernels' precision
+        gr = oops.act_bwd(pre, host(dX).astype(np.float64), oin, 0.2)
+        _, rdg, rdb = oa.bn_bwd(B, xpre, gr, gi, mi, ii)
+        check(host(S)[:, 0], rdb, f32_tol(dtype), "input block's sum g")
+        check(host(S)[:, 1], rdg, f32_tol(dtype), "input block's sum g xhat")
+    else:
+        with pytest.raises(RuntimeError):
+            hb.conv1x1_bn_prenorm_bwd(B, Nb, Ci, Co, L, DT[dtype], Xp, xs, Gi, Bi, MI, II, in_act, 0.2, W, out["prenorm"]["Z"], zs,
+                                      dY, zs, G, Bt, out["prenorm"]["SM"], out["prenorm"]["SI"], out["prenorm"]["dX"], xs,
+                                      out["prenorm"]["dW"], out["prenorm"]["db"], out["prenorm"]["dG"], out["prenorm"]["dB"],
+                                      act, 0.2, ws, in_sums=S)
     # an input the kernels do not take comes back as a status code with nothing launched
     with pytest.raises(RuntimeError):
         hb.conv1x1_bn_prenorm_fwd(B, Nb, Ci, Co, L, DT["f32"], Xp, xs, Gi, Bi, MI, II, in_act, 0.2, W, Bs, G, Bt, 1e-5, 0.1,

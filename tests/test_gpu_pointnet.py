@@ -448,7 +448,11 @@ def test_partial_fusion_matches_full_fusion(dtype, unfused):
                     scale = max(np.abs(gf).max(), 1e-30)
                     if zero_grad_param(spec, name):
                         continue
-                    assert np.abs(gf - gp).max() <= 2e-5 * scale, (name, b)
+                    # (the fused chain hands each layer's two BatchNorm reductions down from its successor's kernel,
+                    # the model-by-model layers take them in their own pass: a different fp32 summation order of the
+                    # means, which moves single bf16 roundings of dz in the layers below)
+                    # -- each flip is one bf16 ulp of a dz element, 2^-8 of it; a weight gradient sums thousands)
+                    assert np.abs(gf - gp).max() <= (2e-5 if dtype == "f32" else 3e-4) * scale, (name, b)
     for name, _ in full.shapes:
         for b in range(spec.B):
             tf, tp = full.param_host(full.theta, name, b), part.param_host(part.theta, name, b)

