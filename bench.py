@@ -97,11 +97,11 @@ def kernel_label(name, a):
     if name == "conv1x1_bn_prenorm_fwd":     # the same kernels as the plain call, the input normalised on load
         return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_fwd_conv_part_kernel"
     if name == "conv1x1_bn_prenorm_bwd":
-        return "conv1x1_bn_bwd: bn_bwd_conv_coef_kernel + cbb_kernel + cbb_reduce_kernel"
+        return "conv1x1_bn_bwd: bn_bwd_conv_coef_kernel or bn_bwd_coef_sums_kernel + cbb_kernel + cbb_reduce_kernel"
     if name == "conv1x1_bn_bwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci <= 128 and Co <= 128 and L % 4 == 0:
-            return "conv1x1_bn_bwd: bn_bwd_conv_coef_kernel + cbb_kernel + cbb_reduce_kernel"
+            return "conv1x1_bn_bwd: bn_bwd_conv_coef_kernel or bn_bwd_coef_sums_kernel + cbb_kernel + cbb_reduce_kernel"
         return "conv1x1_bn_bwd: bn_bwd_conv_kernel + conv1x1 backward kernels"
     if name == "conv1x1_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
@@ -279,7 +279,10 @@ def algorithmic_bytes(name, a):
         B, Nb, Ci, Co, L, dt = a[:6]
         y = a[20] if name == "conv1x1_bn_fwd" else a[26]
         return (B * Nb * (Ci + (3 if y is not None else 1) * Co) * L + B * Co * (Ci + 1)) * _es(dt)
-    if name in ("conv1x1_bn_bwd", "conv1x1_bn_prenorm_bwd"):   # dY, z in (the batch means), then dY, z, x in and dX out; dz itself is not counted
+    if name in ("conv1x1_bn_bwd", "conv1x1_bn_prenorm_bwd"):
+        # BatchNorm backward as the method defines it reads dY and z twice (the batch means, then the gradient);
+        # then x in and dX out; dz itself is not counted.  (Where the successor's kernel hands the two means' sums
+        # down, the first read does not happen: the counters' traffic is then below this figure.)
         B, Nb, Ci, Co, L, dt = a[:6]
         has_dx = (a[17] if name == "conv1x1_bn_bwd" else a[23]) is not None
         return (B * Nb * (4 * Co + (2 if has_dx else 1) * Ci) * L + B * Co * Ci) * _es(dt) + B * Co * (Ci + 3) * 4
