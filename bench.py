@@ -92,10 +92,10 @@ def kernel_label(name, a):
     if name == "conv1x1_bn_fwd":
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci % 8 == 0 and L % 4 == 0 and ((Ci <= 128 and Co >= 64) or (Ci <= 256 and Co >= 512)):
-            return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_fwd_conv_part_kernel"
+            return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_stats_part_kernel (+ bn_apply_conv_kernel)"
         return "conv1x1_bn_fwd: conv1x1 kernel + bn_fwd_conv_kernel"
     if name == "conv1x1_bn_prenorm_fwd":     # the same kernels as the plain call, the input normalised on load
-        return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_fwd_conv_part_kernel"
+        return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_stats_part_kernel (+ bn_apply_conv_kernel)"
     if name == "conv1x1_bn_prenorm_bwd":
         return "conv1x1_bn_bwd: bn_bwd_conv_coef_kernel or bn_bwd_coef_sums_kernel + cbb_kernel + cbb_reduce_kernel"
     if name == "conv1x1_bn_bwd":
@@ -387,6 +387,11 @@ def ops_report(torch, binding):
     MFMA_PEAK = 2500.0          # TFLOP/s, dense bf16
 
     def timeit(fn, n=100, warm=30):
+        # the first entry timed after new tensors were made ran 10-20 % slow with 30 warm-up launches alone (clocks
+        # and caches had not settled): a few milliseconds of the same launches first, then the warm-up proper
+        for _ in range(3 * warm):
+            fn()
+        torch.cuda.synchronize()
         for _ in range(warm):
             fn()
         s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -434,9 +439,9 @@ def ops_report(torch, binding):
         for name, fn in (("conv2d_fwd", lambda: hb.conv2d_grouped_fwd(*geo, X, W, None, Y, workspace=ws)),
                          ("conv2d_dX", lambda: hb.conv2d_grouped_bwd(*geo, None, W, dY, dX, None, None, ws)),
                          ("conv2d_dW", lambda: hb.conv2d_grouped_bwd(*geo, X, None, dY, None, dW, None, ws)),
-                         ("conv2d_fwd (implicit GEMM, no workspace)", lambda: hb.conv2d_grouped_fwd(*geo, X, W, None, Y)),
-                         ("conv2d_dX (implicit GEMM, no workspace)", lambda: hb.conv2d_grouped_bwd(*geo, None, W, dY, dX, None, None, None)),
-                         ("conv2d_dW (implicit GEMM, minimal workspace)", lambda: hb.conv2d_grouped_bwd(*geo, X, None, dY, None, dW, None, wmin))):
+                         ("conv2d_fwd (no workspace: no split of the reduction)", lambda: hb.conv2d_grouped_fwd(*geo, X, W, None, Y)),
+                         ("conv2d_dX (no workspace: fallback that gathers single taps, no regrouped weights)", lambda: hb.conv2d_grouped_bwd(*geo, None, W, dY, dX, None, None, None)),
+                         ("conv2d_dW (minimal workspace: fewest partial slices)", lambda: hb.conv2d_grouped_bwd(*geo, X, None, dY, None, dW, None, wmin))):
             t = timeit(fn)
             out.append(dict(op=name, workload=f"c3 B=10 Nb=64 {ci}->{co} {H}x{H} k4 s2 p1 bf16", ms=t * 1e3, bound="mfma",
                             achieved=fl / t / 1e12, peak=MFMA_PEAK, unit="TFLOP/s", frac=fl / t / 1e12 / MFMA_PEAK))
@@ -746,7 +751,7 @@ def main():
                 json.dump(ops, f, indent=1)
         if args.workload == "all":
             out["operators"] = ops
-            out["operators_note"] = ("entry points timed alone with HIP events (30 warm-up + 100 launches): fused Linear at "
+            out["operators_note"] = ("entry points timed alone with HIP events (120 warm-up + 100 launches): fused Linear at "
                                      "config 4 shapes, grouped conv2d at config 3 shapes, against the dense bf16 MFMA peak")
     print(json.dumps(out))
 

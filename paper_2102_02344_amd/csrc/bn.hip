@@ -123,59 +123,49 @@ __global__ __launch_bounds__(NT) void bn_apply_conv_kernel(BnFwdArgs p) {
   }
 }
 
-// The same forward with its statistics taken from partial sums that the producing convolution left
-// behind (sums of (x - shift) and (x - shift)^2 per slice, shift = the channel's conv bias or 0):
-// the channel is read once, for the normalisation.
-template <typename T, int VEC, int NT>
-__global__ __launch_bounds__(NT) void bn_fwd_conv_part_kernel(BnFwdArgs p, const float* __restrict__ part, int parts,
-                                                              const T* __restrict__ shift_v) {
-  __shared__ float sh[NT / 64][2];
-  const int c = blockIdx.x, b = blockIdx.y;
-  const T* x = reinterpret_cast<const T*>(p.X) + b * p.xsb + c * p.xsc;
-  T* y = reinterpret_cast<T*>(p.Y) + b * p.ysb + c * p.ysc;
-  const int chunks = p.L / VEC;
-  const int k = b * p.C + c;
-  const float shift = shift_v ? Elem<T>::load(shift_v + k) : 0.f;
+// Training statistics from partial sums that the producing convolution left behind (sums of (x - shift) and
+// (x - shift)^2 per slice, shift = the channel's conv bias or 0), so that the tensor is read once, for the
+// normalisation (bn_apply_conv_kernel), or not at all (a consumer normalises on load).  The partials lie
+// [part][channel], so a workgroup takes 16 neighbouring channels -- 16 lanes read 128 contiguous bytes of one
+// part, 64 such rows are in flight per step -- instead of one channel whose parts are a channel count apart.
+// Per-lane sums in a fixed order, then a fixed-order tree over the 64 part lanes.
+constexpr int BNS_C = 16, BNS_P = 64;
+__global__ __launch_bounds__(BNS_C * BNS_P) void bn_stats_part_kernel(BnFwdArgs p, const float* __restrict__ part, int parts,
+                                                                      const bf16_raw* __restrict__ shift_v) {
+  __shared__ float2 red[BNS_P][BNS_C];
+  const int cl = threadIdx.x & (BNS_C - 1), pl = threadIdx.x / BNS_C;
+  const int c = blockIdx.x * BNS_C + cl, b = blockIdx.y;
+  const bool live = c < p.C;
+  const float2* pp = reinterpret_cast<const float2*>(part) + (int64_t)b * parts * p.C + (live ? c : 0);
   float s1 = 0.f, s2 = 0.f;
-  const float2* pp = reinterpret_cast<const float2*>(part) + (int64_t)b * parts * p.C + c;
-  for (int i = threadIdx.x; i < parts; i += NT) {       // fixed order per thread, fixed-order block sum
+#pragma unroll 4
+  for (int i = pl; i < parts; i += BNS_P) {
     const float2 v = pp[(int64_t)i * p.C];
     s1 += v.x; s2 += v.y;
   }
-  block_sum2<NT / 64>(s1, s2, sh);
-  const float m = (float)p.Nb * (float)p.L;
-  const float dm = s1 / m;
-  const float mean = shift + dm;
-  float var = s2 / m - dm * dm;
-  var = var < 0.f ? 0.f : var;
-  const float invstd = 1.0f / sqrtf(var + p.eps);
-  const float g = p.gamma[k], bt = p.beta[k];
-  if (threadIdx.x == 0) {
-    p.save_mean[k] = mean;
-    p.save_invstd[k] = invstd;
-    if (p.running_mean) {
-      const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
-      p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
-      p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
+  red[pl][cl] = make_float2(s1, s2);
+  __syncthreads();
+  for (int h = BNS_P / 2; h > 0; h >>= 1) {
+    if (pl < h) {
+      const float2 a = red[pl][cl], o = red[pl + h][cl];
+      red[pl][cl] = make_float2(a.x + o.x, a.y + o.y);
     }
+    __syncthreads();
   }
-  if (!p.Y) return;                      // statistics only: a consumer normalises on load
-  for (RowWalk w(chunks, NT); w.n < p.Nb;) {
-    float v[BN_UNROLL][VEC];
-    int n[BN_UNROLL], ch[BN_UNROLL];
-#pragma unroll
-    for (int u = 0; u < BN_UNROLL; ++u) {
-      n[u] = w.n; ch[u] = w.ch;
-      load_vec<T, VEC>(n[u] < p.Nb ? x + n[u] * p.xsn + ch[u] * VEC : x, v[u]);
-      w.step();
-    }
-#pragma unroll
-    for (int u = 0; u < BN_UNROLL; ++u)
-      if (n[u] < p.Nb) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) v[u][e] = apply_act(fmaf(g, (v[u][e] - mean) * invstd, bt), p.act, p.slope);
-        store_vec<T, VEC>(y + n[u] * p.ysn + ch[u] * VEC, v[u]);
-      }
+  if (pl != 0 || !live) return;
+  const int k = b * p.C + c;
+  const float shift = shift_v ? bf16_to_f32(shift_v[k]) : 0.f;
+  const float m = (float)p.Nb * (float)p.L;
+  const float dm = red[0][cl].x / m;
+  const float mean = shift + dm;
+  float var = red[0][cl].y / m - dm * dm;
+  var = var < 0.f ? 0.f : var;
+  p.save_mean[k] = mean;
+  p.save_invstd[k] = 1.0f / sqrtf(var + p.eps);
+  if (p.running_mean) {
+    const float unb = m > 1.f ? var * (m / (m - 1.f)) : var;
+    p.running_mean[k] = (1.f - p.momentum) * p.running_mean[k] + p.momentum * mean;
+    p.running_var[k] = (1.f - p.momentum) * p.running_var[k] + p.momentum * unb;
   }
 }
 
@@ -463,7 +453,7 @@ int layout_kind(const int64_t* s, int L) {
 
 
 namespace hfta {
-// see bn_fwd_conv_part_kernel; conv layout only, bf16 (the producer is the streaming convolution)
+// see bn_stats_part_kernel; conv layout only, bf16 (the producer is the streaming convolution)
 int bn_fwd_from_partials(int B, int Nb, int C, int L, int dtype, const void* X, const int64_t xs[4], const float* gamma,
                          const float* beta, float eps, float momentum, float* running_mean, float* running_var,
                          float* save_mean, float* save_invstd, void* Y, const int64_t ys[4], int act, float slope,
@@ -472,14 +462,18 @@ int bn_fwd_from_partials(int B, int Nb, int C, int L, int dtype, const void* X, 
   if (dtype != HFTA_BF16 || B > 65535 || layout_kind(xs, L) != 1 || (Y && layout_kind(ys, L) != 1)) return HFTA_EUNSUPPORTED;
   BnFwdArgs a{X, Y, gamma, beta, running_mean, running_var, save_mean, save_invstd,
               xs[0], xs[1], xs[2], Y ? ys[0] : 0, Y ? ys[1] : 0, Y ? ys[2] : 0, Nb, C, L, act, eps, momentum, slope};
-  const dim3 grid((unsigned)C, (unsigned)B);
-  const bool v4 = vec_ok(X, xs, L, dtype) && (!Y || vec_ok(Y, ys, L, dtype));
-  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
   const bf16_raw* sv = (const bf16_raw*)shift;
-  if (v4) { if (big) hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 4, 1024>), grid, dim3(1024), 0, st, a, part, parts, sv);
-            else hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 4, 256>), grid, dim3(256), 0, st, a, part, parts, sv); }
-  else { if (big) hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 1, 1024>), grid, dim3(1024), 0, st, a, part, parts, sv);
-         else hipLaunchKernelGGL((bn_fwd_conv_part_kernel<bf16_raw, 1, 256>), grid, dim3(256), 0, st, a, part, parts, sv); }
+  hipLaunchKernelGGL(bn_stats_part_kernel, dim3((unsigned)((C + BNS_C - 1) / BNS_C), (unsigned)B), dim3(BNS_C * BNS_P), 0, st, a, part,
+                     parts, sv);
+  const int rc = launch_status();
+  if (!Y || rc != HFTA_OK) return rc;
+  const dim3 grid((unsigned)C, (unsigned)B);
+  const bool v4 = vec_ok(X, xs, L, dtype) && vec_ok(Y, ys, L, dtype);
+  const bool big = bn_wide_block((int64_t)Nb * L * dtype_size(dtype));
+  if (v4) { if (big) hipLaunchKernelGGL((bn_apply_conv_kernel<bf16_raw, 4, 1024>), grid, dim3(1024), 0, st, a);
+            else hipLaunchKernelGGL((bn_apply_conv_kernel<bf16_raw, 4, 256>), grid, dim3(256), 0, st, a); }
+  else { if (big) hipLaunchKernelGGL((bn_apply_conv_kernel<bf16_raw, 1, 1024>), grid, dim3(1024), 0, st, a);
+         else hipLaunchKernelGGL((bn_apply_conv_kernel<bf16_raw, 1, 256>), grid, dim3(256), 0, st, a); }
   return launch_status();
 }
 
