@@ -397,6 +397,7 @@ def test_conv1x1_bn_bwd(hb, dtype, B, Nb, Ci, Co, L, act, want_dx):
     (3, 2, 64, 128, 300, 1, 1, True),    # 64 -> 128 with the activated output stored (what feeds the one-operator tail)
     (2, 2, 128, 128, 644, 2, 0, False),  # 128-deep reduction, LeakyReLU on the input block, none on this one
     (2, 2, 24, 72, 132, 0, 2, True),     # channel counts below the tiles, no activation on the input block
+    (2, 3, 32, 64, 260, 2, 1, False),    # LeakyReLU on the input block where its sums are handed down
 ])
 def test_conv1x1_bn_prenorm(hb, B, Nb, Ci, Co, L, in_act, act, want_y):
     """A chain of conv -> BatchNorm -> act blocks in which the activated tensor between two blocks is never
