@@ -93,7 +93,7 @@ def kernel_label(name, a):
         B, Nb, Ci, Co, L, dt = a[:6]
         if dt == 1 and Ci % 8 == 0 and L % 4 == 0 and ((Ci <= 128 and Co >= 64) or (Ci <= 256 and Co >= 512)):
             return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_stats_part_kernel (+ bn_apply_conv_kernel)"
-        return "conv1x1_bn_fwd: conv1x1 kernel + bn_fwd_conv_kernel"
+        return "conv1x1_bn_fwd: conv1x1 kernel (batched GEMM, + statistics in its 256x256 form; K <= 4: vector kernel) + BatchNorm kernels"
     if name == "conv1x1_bn_prenorm_fwd":     # the same kernels as the plain call, the input normalised on load
         return "conv1x1_bn_fwd: conv1x1_stream_kernel(+statistics) + bn_stats_part_kernel (+ bn_apply_conv_kernel)"
     if name == "conv1x1_bn_prenorm_bwd":

@@ -50,6 +50,12 @@ struct GemmDesc {
   // (n / c_seg) * c_seg_stride + n % c_seg past the row start (an [N][C][HW] image tensor seen as [C][N*HW])
   int c_seg;
   int64_t c_seg_stride;
+  // BatchNorm statistics of the output taken in the epilogue (bf16 k=1 convolution forward in the persistent
+  // 256 x 256 kernel only): per (group, 256-column tile, row m) the sums of (c - bias[m]) and (c - bias[m])^2 over
+  // the tile's columns, [G0*G1][tiles_n][M][2] floats, from the values as they are stored.  *stat_done is set
+  // when the kernel that writes them was launched (otherwise nothing touched stat_part).
+  float* stat_part;
+  bool* stat_done;
 };
 
 struct GemmArgs {
@@ -71,6 +77,7 @@ struct GemmArgs {
   uint32_t c_extent;             // same for one output slice, or 0 when it does not fit 31 bits
   int c_seg;
   int64_t c_seg_stride;
+  float* stat_part;              // see GemmDesc
 };
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;

@@ -125,6 +125,8 @@ int gemm_launch(const GemmDesc& d, hipStream_t st) {
   a.act = d.act; a.slope = d.slope;
   a.a_extent = a.b_extent = 0;
   a.c_seg = d.c_seg; a.c_seg_stride = d.c_seg_stride;
+  a.stat_part = d.stat_part;
+  if (d.stat_done) *d.stat_done = false;
 
   // vector-load eligibility: every address the fast path forms must be aligned
   const int es = (int)dtype_size(d.dtype);

@@ -424,8 +424,15 @@ __device__ __forceinline__ void bigp_store_rows(const unsigned char* smem, __amd
 
 struct BigCoord { int m0, n0, g0, g1, split, g, t_begin, t_end; };
 
-template <bool A_KC, bool B_KC, typename OutT, bool COLB, int ACT, bool V16, bool N16>
+// STATS (2-byte output, row bias or none, no activation): while a tile sits staged in LDS on its way out, two
+// threads per row add its 256 stored values and their squares (two-element dot products), origin moved to the
+// row's bias, and leave one pair per (group, column tile, row): the BatchNorm that follows a k=1 convolution
+// takes its statistics from these and reads the output once.  Columns past N hold the bias itself (their B
+// operand was read as zeros) and add nothing to the shifted sums.
+typedef __bf16 big_bf16x2 __attribute__((ext_vector_type(2)));
+template <bool A_KC, bool B_KC, typename OutT, bool COLB, int ACT, bool V16, bool N16, bool STATS = false>
 __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int vgx, int vtotal) {
+  static_assert(!STATS || (sizeof(OutT) == 2 && !COLB && ACT == BIG_NONE && BIG_THREADS == 512), "statistics epilogue: bf16 out, row bias, no activation");
   __shared__ __attribute__((aligned(16))) unsigned char smem[BIG_SMEM];
   __shared__ uint2 sbias[64];                            // this tile's 256 column biases (an object of its own:
                                                          // its reads need not wait for the staging writes)
@@ -648,6 +655,29 @@ __global__ __launch_bounds__(BIG_THREADS) void gemm_bigp_kernel(GemmArgs p, int 
         __syncthreads();
         if (vb == 16) bigp_store_rows<OutT, 16>(smem, rc, c_ldb, p.M, cur.m0 + pass * RP, col_byte, t);
         else bigp_store_rows<OutT, 8>(smem, rc, c_ldb, p.M, cur.m0 + pass * RP, col_byte, t);
+        if constexpr (STATS) {             // RP == 256: the whole tile is staged in this one pass
+          const int row = t >> 1, half = t & 1, m = cur.m0 + row;
+          const unsigned char* src = smem + row * PITCH + half * 256;
+          const big_bf16x2 ones = __builtin_bit_cast(big_bf16x2, 0x3f803f80u);
+          float s1 = 0.f, s2 = 0.f;
+#pragma unroll 8
+          for (int q = 0; q < 32; ++q) {
+            const uint2 v = *reinterpret_cast<const uint2*>(src + q * 8);
+            const big_bf16x2 lo = __builtin_bit_cast(big_bf16x2, v.x), hi = __builtin_bit_cast(big_bf16x2, v.y);
+            s1 = __builtin_amdgcn_fdot2_f32_bf16(lo, ones, s1, false);
+            s2 = __builtin_amdgcn_fdot2_f32_bf16(lo, lo, s2, false);
+            s1 = __builtin_amdgcn_fdot2_f32_bf16(hi, ones, s1, false);
+            s2 = __builtin_amdgcn_fdot2_f32_bf16(hi, hi, s2, false);
+          }
+          const bf16_raw* rb_ = p.bias ? reinterpret_cast<const bf16_raw*>(p.bias) + cur.g0 * p.bias_g0 + cur.g1 * p.bias_g1 : nullptr;
+          const float shift = (rb_ && m < p.M) ? bf16_to_f32(rb_[m]) : 0.f;
+          s2 = fmaf(shift, fmaf(128.f, shift, -2.f * s1), s2);   // sum (c - b)^2 = sum c^2 - 2 b sum c + 128 b^2
+          s1 = fmaf(-128.f, shift, s1);
+          s1 += __shfl_xor(s1, 1, 64);
+          s2 += __shfl_xor(s2, 1, 64);
+          if (half == 0 && m < p.M)
+            *reinterpret_cast<float2*>(p.stat_part + (((int64_t)cur.g * p.tiles_n + cur.n0 / BIG_BN) * p.M + m) * 2) = make_float2(s1, s2);
+        }
         __syncthreads();
       }
     }

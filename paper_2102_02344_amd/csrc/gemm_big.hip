@@ -28,6 +28,13 @@ static int persistent_blocks() {
 
 template <bool A_KC, bool B_KC, typename OutT, bool COLB, bool V16, bool N16>
 static void launch_bigp2(const GemmArgs& a, bool ident, dim3 grid, int blocks, hipStream_t st) {
+  if constexpr (A_KC && !B_KC && std::is_same<OutT, bf16_raw>::value && !COLB && V16) {
+    if (ident && a.stat_part) {          // k=1 convolution forward with the statistics epilogue
+      hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_NONE, V16, N16, true>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0,
+                         st, a, (int)grid.x, (int)(grid.x * grid.z));
+      return;
+    }
+  }
   if (ident)
     hipLaunchKernelGGL((gemm_bigp_kernel<A_KC, B_KC, OutT, COLB, BIG_NONE, V16, N16>), dim3((unsigned)blocks), dim3(BIG_THREADS), 0, st, a,
                        (int)grid.x, (int)(grid.x * grid.z));
@@ -84,7 +91,9 @@ int gemm_big_launch(const GemmDesc& d, const GemmArgs& a0, bool v16, bool n16, d
       if (d.a_kc && !d.b_kc) {
         if (colb) launch_bigp<true, false, bf16_raw, true>(a, ident, v16, n16, grid, blocks, st);
         else launch_bigp<true, false, bf16_raw, false>(a, ident, v16, n16, grid, blocks, st);
-        return launch_status();
+        const int rc = launch_status();
+        if (rc == HFTA_OK && !colb && ident && a.stat_part && a.splits == 1 && d.stat_done) *d.stat_done = true;
+        return rc;
       }
       if (!colb && d.a_kc && d.b_kc) { launch_bigp<true, true, bf16_raw, false>(a, ident, v16, n16, grid, blocks, st); return launch_status(); }
       if (!colb && !d.a_kc && !d.b_kc) { launch_bigp<false, false, bf16_raw, false>(a, ident, v16, n16, grid, blocks, st); return launch_status(); }

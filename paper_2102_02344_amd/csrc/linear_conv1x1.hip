@@ -409,9 +409,11 @@ static int check_conv1x1(int B, int Nb, int Ci, int Co, int L, int dtype) {
   return HFTA_OK;
 }
 
-int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
-                     const void* W, const void* bias, void* Y, const int64_t ys[4], int act, float act_slope,
-                     void* stream) {
+// stat_part / stat_done: see GemmDesc (only the GEMM path's persistent kernel can fill them)
+static int conv1x1_fwd_impl(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                            const void* W, const void* bias, void* Y, const int64_t ys[4], int act, float act_slope,
+                            void* stream, float* stat_part, bool* stat_done) {
+  if (stat_done) *stat_done = false;
   int rc = check_conv1x1(B, Nb, Ci, Co, L, dtype);
   if (rc != HFTA_OK) return rc;
   if (!X || !W || !Y || !xs || !ys || !valid_act(act)) return HFTA_EINVAL;
@@ -438,7 +440,14 @@ int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void
   d.c_ld = ys[2]; d.c_g0 = ys[0]; d.c_g1 = ys[1];
   d.bias = bias; d.bias_mode = 1; d.bias_g0 = Co; d.bias_g1 = 0;
   d.act = act; d.slope = act_slope;
+  d.stat_part = stat_part; d.stat_done = stat_done;
   return gemm_launch(d, as_stream(stream));
+}
+
+int hfta_conv1x1_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const void* X, const int64_t xs[4],
+                     const void* W, const void* bias, void* Y, const int64_t ys[4], int act, float act_slope,
+                     void* stream) {
+  return conv1x1_fwd_impl(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Y, ys, act, act_slope, stream, nullptr, nullptr);
 }
 
 // A k=1 convolution over [per-point maps | a vector tiled along the points] is the convolution over the
@@ -486,16 +495,24 @@ int hfta_conv1x1_bn_fwd(int B, int Nb, int Ci, int Co, int L, int dtype, const v
   if (xs[3] != 1 || zs[3] != 1 || (Y && ys[3] != 1)) return HFTA_EUNSUPPORTED;
   hipStream_t st = as_stream(stream);
   const size_t need = hfta_conv1x1_bn_fwd_workspace_bytes(B, Nb, Ci, Co, L, dtype);
+  float* part = nullptr;
   if (dtype == HFTA_BF16 && need && workspace && ws_bytes >= need && reinterpret_cast<uintptr_t>(workspace) % 8 == 0) {
-    float* part = reinterpret_cast<float*>(workspace);
+    part = reinterpret_cast<float*>(workspace);
     rc = hfta::conv1x1_stream_fwd(B, Nb, Ci, Co, L, X, xs, W, bias, Z, zs, HFTA_ACT_NONE, 0.f, st, part);
     if (rc == HFTA_OK)
       rc = hfta::bn_fwd_from_partials(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var,
                                       save_mean, save_invstd, Y, ys, act, act_slope, part, Nb * ((L + 127) / 128), bias, st);
     if (rc != HFTA_EUNSUPPORTED) return rc;
   }
-  rc = hfta_conv1x1_fwd(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, HFTA_ACT_NONE, 0.f, stream);
+  // wide layers: the batched GEMM; its persistent 256 x 256 kernel leaves the same partial sums per 256-point tile
+  bool stats = false;
+  rc = conv1x1_fwd_impl(B, Nb, Ci, Co, L, dtype, X, xs, W, bias, Z, zs, HFTA_ACT_NONE, 0.f, stream, part, &stats);
   if (rc != HFTA_OK) return rc;
+  if (stats) {
+    rc = hfta::bn_fwd_from_partials(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var,
+                                    save_mean, save_invstd, Y, ys, act, act_slope, part, Nb * ((L + 255) / 256), bias, st);
+    if (rc != HFTA_EUNSUPPORTED) return rc;
+  }
   if (!Y)
     return hfta::bn_stats_conv(B, Nb, Co, L, dtype, Z, zs, gamma, beta, eps, momentum, running_mean, running_var, save_mean,
                                save_invstd, st);

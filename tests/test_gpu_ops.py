@@ -262,6 +262,7 @@ def test_bn_conv_layout(hb, dtype, B, Nb, C, L, act):
     (2, 2, 64, 128, 300, 2, True),     # single W tile of 128 rows
     (1, 2, 128, 320, 260, 1, False),   # three W tiles (ragged: 320 = 2 * 128 + 64), 128-deep reduction, no conv bias
     (2, 2, 24, 40, 100, 0, True),      # not the streaming kernel's shape: the two operators run one after the other
+    (2, 13, 256, 264, 2500, 1, True),  # a wide layer: the persistent 256 x 256 GEMM kernel leaves the partial sums (ragged row and column tiles)
 ])
 def test_conv1x1_bn_fwd(hb, dtype, B, Nb, Ci, Co, L, act, bias):
     """Conv1d k=1 + training BatchNorm + activation in one call against the composition of the two
