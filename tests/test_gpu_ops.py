@@ -263,6 +263,7 @@ def test_bn_conv_layout(hb, dtype, B, Nb, C, L, act):
     (1, 2, 128, 320, 260, 1, False),   # three W tiles (ragged: 320 = 2 * 128 + 64), 128-deep reduction, no conv bias
     (2, 2, 24, 40, 100, 0, True),      # not the streaming kernel's shape: the two operators run one after the other
     (2, 13, 256, 264, 2500, 1, True),  # a wide layer: the persistent 256 x 256 GEMM kernel leaves the partial sums (ragged row and column tiles)
+    (2, 2, 256, 264, 502, 1, True),    # rows that are only 4-byte aligned (L % 4 == 2): no vector path anywhere
 ])
 def test_conv1x1_bn_fwd(hb, dtype, B, Nb, Ci, Co, L, act, bias):
     """Conv1d k=1 + training BatchNorm + activation in one call against the composition of the two
@@ -314,6 +315,7 @@ def test_conv1x1_bn_fwd(hb, dtype, B, Nb, Ci, Co, L, act, bias):
     (2, 2, 24, 40, 132, 1, True),      # channel counts below the tiles (zero padding inside the kernel)
     (300, 2, 64, 64, 260, 1, True),    # many models: one workgroup per model walks all its slices
     (2, 2, 64, 200, 128, 1, True),     # not the one-pass kernel's shape: the two operators, dz in the workspace
+    (2, 2, 64, 64, 130, 1, True),      # L % 4 == 2: the one-pass kernel's channel counts, but not its alignment
 ])
 def test_conv1x1_bn_bwd(hb, dtype, B, Nb, Ci, Co, L, act, want_dx):
     """BatchNorm backward + k=1 convolution backward in one call against the oracle's chain of the two
